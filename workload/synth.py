@@ -1,0 +1,58 @@
+"""Seeded synthetic FFN workloads.
+
+These stand in for the Llama-style FFN activations and weights of the paper's experiments
+(Table 1 gives d_model / d_ffn for the 1B and 7B models), which need datasets and trained
+weights.  What is reproduced: shapes, bf16 storage, Gaussian statistics and the fraction of
+SquaredReLU outputs that are zero (the paper reports more than 90 %), set through a per-neuron
+pre-activation bias.  Tensors are returned as numpy uint16 bf16 bit patterns.
+"""
+import numpy as np
+
+# name -> (tokens T, d_model D, d_ff F)
+CONFIGS = {
+    "tiny": (512, 256, 1024),        # single small layer; the CPU oracle finishes in well under a second
+    "1b": (8192, 2048, 8192),        # Table 1, Llama 1B FFN; batch 4 x seq 2048
+    "7b": (16384, 4096, 16384),      # Table 1, Llama 7B FFN; batch 4 x seq 4096
+    "70b": (8192, 8192, 28672),      # 70B-scale layer
+    "moe_expert": (16384 * 2 // 8, 4096, 14336),  # one expert's mean share of 16384 tokens routed top-2 over 8
+}
+
+# standard-normal quantiles: P(N(0,1) < z) = zero fraction of the SquaredReLU output
+Z_FOR_ZERO_FRACTION = {0.50: 0.0, 0.75: 0.6744897501960817, 0.90: 1.2815515655446004, 0.95: 1.6448536269514722}
+
+
+def bf16_bits_from_f32(x):
+    """float32 -> bf16 bit pattern, round to nearest even (finite inputs)."""
+    u = np.ascontiguousarray(np.asarray(x, dtype=np.float32)).view(np.uint32)
+    return ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)).astype(np.uint16)
+
+
+def _bits_to_f64(b):
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def make_ffn_inputs(T, D, F, seed=0, zero_fraction=0.90, w_std=0.02):
+    """X [T, D] ~ N(0,1), W1 [F, D] and W2 [D, F] ~ N(0, w_std^2), dY [T, D] ~ N(0,1), all bf16 bits;
+    b1 [F] float32 = -z * s_f where s_f is the standard deviation of neuron f's pre-activation
+    under X ~ N(0,1) once W1's two smallest magnitudes of every four along D are dropped, i.e.
+    the root of the sum, over groups, of the two largest squares."""
+    rng = np.random.default_rng(seed)
+    X = bf16_bits_from_f32(rng.standard_normal((T, D), dtype=np.float32))
+    W1 = bf16_bits_from_f32(rng.standard_normal((F, D), dtype=np.float32) * np.float32(w_std))
+    W2 = bf16_bits_from_f32(rng.standard_normal((D, F), dtype=np.float32) * np.float32(w_std))
+    dY = bf16_bits_from_f32(rng.standard_normal((T, D), dtype=np.float32))
+    z = Z_FOR_ZERO_FRACTION[zero_fraction] if zero_fraction in Z_FOR_ZERO_FRACTION else float(zero_fraction)
+    sq = np.sort((_bits_to_f64(W1) ** 2).reshape(F, D // 4, 4), axis=-1)[..., 2:]
+    b1 = (-z * np.sqrt(sq.sum(axis=(1, 2)))).astype(np.float32)
+    return dict(X=X, W1=W1, W2=W2, b1=b1, dY=dY)
+
+
+def make_moe_segments(n_tokens=16384, n_experts=8, top_k=2, seed=0, align=64):
+    """Top-k routing from N(0,1) logits: per-expert token counts and 64-row-aligned segment offsets."""
+    rng = np.random.default_rng(seed)
+    logits = rng.standard_normal((n_tokens, n_experts), dtype=np.float32)
+    top = np.argsort(-logits, axis=1, kind="stable")[:, :top_k]
+    counts = np.bincount(top.reshape(-1), minlength=n_experts).astype(np.int64)
+    padded = (counts + align - 1) // align * align
+    offsets = np.concatenate([[0], np.cumsum(padded)]).astype(np.int64)
+    return counts, offsets
