@@ -1,0 +1,134 @@
+/*
+ * sparseffn.h — C ABI of the MI355X (gfx950) sparsified Transformer-FFN training step.
+ *
+ * Method: "To 2:4 Sparsity and Beyond" (arXiv 2602.06183), Section 3 "Proposed Design":
+ * Alg. 1 (forward) and Alg. 2 (backward) over eqs. (1)-(8) of Section 2.1, with the 2:4
+ * weight sparsifier of Section 2.2 and the V:N:M activation format of Section 2.3.
+ *
+ * Conventions common to every entry point
+ *   - bf16 tensors are uint16_t bit patterns, row-major; all tensor pointers are DEVICE
+ *     pointers owned by the caller.  The library never allocates, frees or synchronises:
+ *     it only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).  Outputs are fully overwritten.
+ *   - Return value: SFFN_OK, or a negative code with nothing enqueued for SFFN_EINVAL /
+ *     SFFN_EUNSUPPORTED / SFFN_EWORKSPACE.  sffn_last_error() gives a thread-local text.
+ *   - Shape rules: T % 64 == 0, D % 64 == 0, F % 64 == 0 (R, K, N below follow the same
+ *     rule); base pointers 16-byte aligned.  V must be 64 and M must be 8.
+ *   - Rounding: products accumulate in fp32 on the matrix cores; every stored bf16 is one
+ *     round-to-nearest-even of an fp32 value.
+ *
+ * Packed formats (bit-exact contract)
+ *   2:4   logical S[R,K]; group g of row r is S[r,4g..4g+3]; the two entries of largest
+ *         magnitude survive (rank by magnitude descending, index ascending; magnitude is the
+ *         bf16 pattern with the sign cleared, compared as an integer), at positions p0 < p1.
+ *         vals[r,2g] = S[r,4g+p0], vals[r,2g+1] = S[r,4g+p1]; nibble = p0 | p1<<2;
+ *         meta[r,g/2] holds group 2j in bits 3:0 and group 2j+1 in bits 7:4.
+ *   V:N:M (V=64, N=2, M=8) block (tb,g) = rows 64tb..64tb+63, columns 8g..8g+7.  Column
+ *         score = fp32 sum of |y2| over the 64 rows, added in ascending row order from +0.
+ *         The four columns of largest score survive (ties to the lower column);
+ *         colidx[tb,g,0..3] are their offsets in ascending order.  Per row those four
+ *         entries form one 2:4 group packed as above: vals[t,2g..2g+1], meta[t,g/2].
+ */
+#ifndef SPARSEFFN_H
+#define SPARSEFFN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SFFN_OK            0
+#define SFFN_EINVAL       (-1)  /* null pointer, bad shape or alignment */
+#define SFFN_EUNSUPPORTED (-2)  /* valid request outside what is built (V != 64, M != 8, ...) */
+#define SFFN_EWORKSPACE   (-3)  /* workspace pointer null or too small */
+#define SFFN_EHIP         (-4)  /* a HIP launch failed; see sffn_last_error() */
+
+#define SFFN_MODE_HARD 0        /* Section 2.2, plain magnitude mask */
+#define SFFN_MODE_SOFT 1        /* Section 2.2, soft-thresholding: survivors shrink by t = |t2| */
+
+typedef struct sffn_cfg {
+    int64_t T;      /* tokens (rows of X, dY) */
+    int64_t D;      /* d_model */
+    int64_t F;      /* d_ffn */
+    int32_t V;      /* V:N:M block height, 64 */
+    int32_t M;      /* V:N:M block width, 8 */
+    int32_t mode;   /* SFFN_MODE_HARD or SFFN_MODE_SOFT for both weight sparsifiers */
+    int32_t reserved;
+} sffn_cfg;
+
+/* Byte offsets, inside the workspace of ffn_sparse_step, of the tensors Alg. 2 line 1 saves
+ * from the forward pass and of the other intermediates (all filled when the step returns). */
+typedef struct sffn_ws_layout {
+    size_t w1_vals, w1_meta;        /* sparsify24(W1):   [F, D/2] bf16, [F, D/8] u8 */
+    size_t w2t_vals, w2t_meta;      /* sparsify24(W2.T): [F, D/2] bf16, [F, D/8] u8 */
+    size_t y1;                      /* [T, F] bf16, eq. (1) plus bias */
+    size_t y2_vals, y2_meta, colidx;/* V:N:M y2: [T, F/4] bf16, [T, F/16] u8, [T/64, F/8, 4] u8 */
+    size_t dy2;                     /* [T, F] bf16, eq. (4) */
+    size_t dy1_vals;                /* [T, F/4] bf16, eq. (6) in y2's slots */
+    size_t total;                   /* bytes needed */
+} sffn_ws_layout;
+
+int         sffn_version(void);
+const char* sffn_last_error(void);
+
+/* Workspace sizes in bytes (0 on invalid arguments). */
+size_t sffn_workspace_bytes(const sffn_cfg* cfg);                       /* ffn_sparse_step */
+int    sffn_workspace_layout(const sffn_cfg* cfg, sffn_ws_layout* out); /* its layout */
+size_t sffn_vnm_spmm_workspace_bytes(int64_t T, int64_t N, int64_t Kfull, int w_kmajor);
+size_t sffn_vnm_wgrad_workspace_bytes(int64_t T, int64_t F, int64_t N);
+
+/* Section 2.2 / Alg. 1 line 4 and Alg. 2 line 2 (sparsify24): 2:4 prune-and-pack along K.
+ * Logical S[R,K]: trans=0 -> S[r,k] = src[r*ld + k]; trans=1 -> S[r,k] = src[k*ld + r]
+ * (so sparsify24(W2.T) reads W2 [D,F] in place with R=F, K=D, ld=F).
+ * out: vals [R,K/2] bf16, meta [R,K/8] u8.  mode SOFT: survivor a -> a -/+ t evaluated in fp32
+ * then rounded to bf16, t = third-largest magnitude of the group; same metadata as HARD. */
+int prune24_compress(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode,
+                     uint16_t* vals, uint8_t* meta, void* stream);
+
+/* eq. (2) + Section 2.3 / Alg. 1 lines 5-6: y2 = bf16(max(y1,0)^2) compressed on the fly to V:N:M.
+ * y1 [T,F]; out vals [T,F/4], meta [T,F/16], colidx [T/64,F/8,4]. */
+int sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, int V, int M,
+                        uint16_t* vals, uint8_t* meta, uint8_t* colidx, void* stream);
+
+/* eq. (1) / Alg. 1 line 4: out[t,n] = bf16( sum_k X[t,k] * Ws[n,k] + bias[n] ), Ws packed 2:4
+ * ([N,K/2], [N,K/8]); bias fp32 [N] or NULL; X [T,K]; out [T,N]. */
+int spmm24_fwd(const uint16_t* X, const uint16_t* w_vals, const uint8_t* w_meta, const float* bias,
+               int64_t T, int64_t N, int64_t K, uint16_t* out, void* stream);
+
+/* eq. (4) / Alg. 2 line 2: out[t,n] = bf16( sum_k dY[t,k] * WTs[n,k] ), WTs = packed sparsify24(W2.T). */
+int spmm24_dgrad(const uint16_t* dY, const uint16_t* wt_vals, const uint8_t* wt_meta,
+                 int64_t T, int64_t N, int64_t K, uint16_t* out, void* stream);
+
+/* eq. (3) / Alg. 1 line 7 (w_kmajor=0, Wd = W2 [N,Kfull]) and eq. (7) / Alg. 2 line 5
+ * (w_kmajor=1, Wd = W1 [Kfull,N]): out[t,n] = bf16( sum_f Av[t,f] * W(n,f) ) with Av the V:N:M
+ * matrix (a_vals [T,Kfull/4], a_meta [T,Kfull/16], a_colidx [T/64,Kfull/8,4]) and W dense.
+ * ldw = row stride of Wd in elements.  workspace: sffn_vnm_spmm_workspace_bytes(). */
+int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_colidx,
+             const uint16_t* Wd, int64_t ldw, int w_kmajor, int64_t T, int64_t N, int64_t Kfull,
+             int V, int M, uint16_t* out, void* workspace, size_t ws_bytes, void* stream);
+
+/* eq. (6) / Alg. 2 line 4 on y2's mask: dvals[t,s] = bf16( 2 * dy2[t,c] * max(y1[t,c],0) ) where
+ * slot s of row t sits at column c according to (meta, colidx); dvals [T,F/4]. */
+int dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, const uint8_t* colidx,
+                int64_t T, int64_t F, int V, int M, uint16_t* dvals, void* stream);
+
+/* eq. (5) / Alg. 2 line 3 (out_f_major=0: out [N,F] = dW2) and eq. (8) / Alg. 2 line 6
+ * (out_f_major=1: out [F,N] = dW1): C[f,n] = bf16( sum_t Av[t,f] * G[t,n] ), G [T,N] dense.
+ * workspace: sffn_vnm_wgrad_workspace_bytes(). */
+int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_colidx,
+              const uint16_t* G, int64_t T, int64_t F, int64_t N, int V, int M, int out_f_major,
+              uint16_t* out, void* workspace, size_t ws_bytes, void* stream);
+
+/* Alg. 1 + Alg. 2, one call: X [T,D], W1 [F,D], W2 [D,F], b1 fp32 [F] or NULL, dY [T,D] ->
+ * Y3 [T,D], dX [T,D], dW1 [F,D], dW2 [D,F]; intermediates land in `workspace` at the offsets of
+ * sffn_workspace_layout().  Both weight matrices are re-pruned inside the call. */
+int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, const uint16_t* W2,
+                    const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
+                    uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSEFFN_H */

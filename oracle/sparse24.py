@@ -46,7 +46,7 @@ def prune24_compress(bits, mode=HARD):
         t = bits_to_f32(t_bits)                                         # >= 0, [R, G, 1]
         a = bits_to_f32(vals)
         neg = (vals & np.uint16(0x8000)) != 0
-        with np.errstate(invalid="ignore"):
+        with np.errstate(invalid="ignore", over="ignore"):
             shrunk = np.where(neg, a + t, a - t).astype(np.float32)
         vals = f32_to_bits(shrunk)
     elif mode != HARD:

@@ -1,0 +1,9 @@
+"""MI355X (gfx950) sparsified Transformer-FFN training step: thin Python binding over libsparseffn.so.
+
+Every function marshals arguments into the C ABI of include/sparseffn.h; all arithmetic runs in
+the HIP kernels.  torch is used for device memory and streams only.
+"""
+from .binding import (SffnError, lib_path, load, version, workspace_bytes, workspace_layout,
+                      prune24_compress, sqrelu_vnm_compress, spmm24_fwd, spmm24_dgrad, vnm_spmm,
+                      dsqrelu_vnm, vnm_wgrad, ffn_sparse_step, FfnStep,
+                      MODE_HARD, MODE_SOFT)

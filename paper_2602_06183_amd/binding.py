@@ -1,0 +1,213 @@
+"""ctypes binding of libsparseffn.so: argument marshalling only.
+
+bf16 tensors are torch.bfloat16 (or int16/uint16 bit-pattern) CUDA tensors; outputs are allocated
+here with torch.empty and returned.  Kernels are enqueued on torch's current stream.
+"""
+import ctypes
+import os
+
+import torch
+
+MODE_HARD, MODE_SOFT = 0, 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class SffnError(RuntimeError):
+    pass
+
+
+class _Cfg(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int64), ("D", ctypes.c_int64), ("F", ctypes.c_int64), ("V", ctypes.c_int32),
+                ("M", ctypes.c_int32), ("mode", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class _Layout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_size_t) for n in ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta", "y1", "y2_vals", "y2_meta",
+                                               "colidx", "dy2", "dy1_vals", "total")]
+
+
+def lib_path():
+    return os.path.join(_HERE, "libsparseffn.so")
+
+
+def load():
+    """Loads the HIP library; raises if it has not been built (there is no fallback path)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise SffnError("libsparseffn.so is not built: run `python -m paper_2602_06183_amd.build` "
+                        "(or __graft_entry__.build()); there is no CPU fallback")
+    lib = ctypes.CDLL(path)
+    p, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+    lib.sffn_version.restype = ctypes.c_int
+    lib.sffn_last_error.restype = ctypes.c_char_p
+    lib.sffn_workspace_bytes.restype = sz
+    lib.sffn_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg)]
+    lib.sffn_workspace_layout.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_Layout)]
+    lib.sffn_vnm_spmm_workspace_bytes.restype = sz
+    lib.sffn_vnm_spmm_workspace_bytes.argtypes = [i64, i64, i64, i32]
+    lib.sffn_vnm_wgrad_workspace_bytes.restype = sz
+    lib.sffn_vnm_wgrad_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.prune24_compress.argtypes = [p, i64, i64, i64, i32, i32, p, p, p]
+    lib.sqrelu_vnm_compress.argtypes = [p, i64, i64, i32, i32, p, p, p, p]
+    lib.spmm24_fwd.argtypes = [p, p, p, p, i64, i64, i64, p, p]
+    lib.spmm24_dgrad.argtypes = [p, p, p, i64, i64, i64, p, p]
+    lib.vnm_spmm.argtypes = [p, p, p, p, i64, i32, i64, i64, i64, i32, i32, p, p, sz, p]
+    lib.dsqrelu_vnm.argtypes = [p, p, p, p, i64, i64, i32, i32, p, p]
+    lib.vnm_wgrad.argtypes = [p, p, p, p, i64, i64, i64, i32, i32, i32, p, p, sz, p]
+    lib.ffn_sparse_step.argtypes = [ctypes.POINTER(_Cfg)] + [p] * 9 + [p, sz, p]
+    _LIB = lib
+    return lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise SffnError("libsparseffn error %d: %s" % (rc, load().sffn_last_error().decode()))
+
+
+def _ptr(t, rows_strided=False):
+    if t is None:
+        return None
+    ok = t.is_contiguous() or (rows_strided and t.dim() == 2 and t.stride(1) == 1)
+    if not t.is_cuda or not ok:
+        raise SffnError("expected a contiguous device tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _bf16(shape, dev):
+    return torch.empty(shape, dtype=torch.bfloat16, device=dev)
+
+
+def _u8(shape, dev):
+    return torch.empty(shape, dtype=torch.uint8, device=dev)
+
+
+def version():
+    return load().sffn_version()
+
+
+def _cfg(T, D, F, mode=MODE_HARD, V=64, M=8):
+    return _Cfg(T, D, F, V, M, mode, 0)
+
+
+def workspace_bytes(T, D, F, mode=MODE_HARD):
+    c = _cfg(T, D, F, mode)
+    return load().sffn_workspace_bytes(ctypes.byref(c))
+
+
+def workspace_layout(T, D, F, mode=MODE_HARD):
+    c, lay = _cfg(T, D, F, mode), _Layout()
+    _check(load().sffn_workspace_layout(ctypes.byref(c), ctypes.byref(lay)))
+    return {n: getattr(lay, n) for n, _ in _Layout._fields_}
+
+
+def prune24_compress(src, trans=False, mode=MODE_HARD):
+    """src [R, K] (trans=False) or [K, R] (trans=True: groups run down the rows).  -> vals [R, K/2], meta [R, K/8]."""
+    rows, cols = src.shape
+    R, K = (cols, rows) if trans else (rows, cols)
+    vals, meta = _bf16((R, K // 2), src.device), _u8((R, K // 8), src.device)
+    _check(load().prune24_compress(_ptr(src, True), R, K, src.stride(0), int(trans), mode, _ptr(vals), _ptr(meta), _stream()))
+    return vals, meta
+
+
+def sqrelu_vnm_compress(y1, V=64, M=8):
+    T, F = y1.shape
+    vals, meta = _bf16((T, 2 * F // M), y1.device), _u8((T, F // (2 * M)), y1.device)
+    colidx = _u8((T // V, F // M, 4), y1.device)
+    _check(load().sqrelu_vnm_compress(_ptr(y1), T, F, V, M, _ptr(vals), _ptr(meta), _ptr(colidx), _stream()))
+    return vals, meta, colidx
+
+
+def spmm24_fwd(X, w_vals, w_meta, bias=None):
+    T, K = X.shape
+    N = w_vals.shape[0]
+    out = _bf16((T, N), X.device)
+    _check(load().spmm24_fwd(_ptr(X), _ptr(w_vals), _ptr(w_meta), _ptr(bias), T, N, K, _ptr(out), _stream()))
+    return out
+
+
+def spmm24_dgrad(dY, wt_vals, wt_meta):
+    T, K = dY.shape
+    N = wt_vals.shape[0]
+    out = _bf16((T, N), dY.device)
+    _check(load().spmm24_dgrad(_ptr(dY), _ptr(wt_vals), _ptr(wt_meta), T, N, K, _ptr(out), _stream()))
+    return out
+
+
+def vnm_spmm(a_vals, a_meta, a_colidx, Wd, w_kmajor, V=64, M=8):
+    T = a_vals.shape[0]
+    Kfull = a_vals.shape[1] * M // 2
+    N = Wd.shape[1] if w_kmajor else Wd.shape[0]
+    out = _bf16((T, N), a_vals.device)
+    nbytes = load().sffn_vnm_spmm_workspace_bytes(T, N, Kfull, int(w_kmajor))
+    ws = _u8((max(nbytes, 16),), a_vals.device)
+    _check(load().vnm_spmm(_ptr(a_vals), _ptr(a_meta), _ptr(a_colidx), _ptr(Wd, True), Wd.stride(0), int(w_kmajor), T, N, Kfull,
+                           V, M, _ptr(out), _ptr(ws), nbytes, _stream()))
+    return out
+
+
+def dsqrelu_vnm(dy2, y1, meta, colidx, V=64, M=8):
+    T, F = y1.shape
+    dvals = _bf16((T, 2 * F // M), y1.device)
+    _check(load().dsqrelu_vnm(_ptr(dy2), _ptr(y1), _ptr(meta), _ptr(colidx), T, F, V, M, _ptr(dvals), _stream()))
+    return dvals
+
+
+def vnm_wgrad(a_vals, a_meta, a_colidx, G, out_f_major, V=64, M=8):
+    T, N = G.shape
+    F = a_vals.shape[1] * M // 2
+    out = _bf16((F, N) if out_f_major else (N, F), G.device)
+    nbytes = load().sffn_vnm_wgrad_workspace_bytes(T, F, N)
+    ws = _u8((max(nbytes, 16),), G.device)
+    _check(load().vnm_wgrad(_ptr(a_vals), _ptr(a_meta), _ptr(a_colidx), _ptr(G), T, F, N, V, M, int(out_f_major), _ptr(out),
+                            _ptr(ws), nbytes, _stream()))
+    return out
+
+
+class FfnStep:
+    """Pre-allocated outputs and workspace for repeated ffn_sparse_step calls on one shape."""
+
+    def __init__(self, T, D, F, mode=MODE_HARD, device="cuda"):
+        self.T, self.D, self.F, self.mode = T, D, F, mode
+        self.cfg = _cfg(T, D, F, mode)
+        self.layout = workspace_layout(T, D, F, mode)
+        self.ws = _u8((self.layout["total"],), device)
+        self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
+        self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
+
+    def __call__(self, X, W1, W2, b1, dY):
+        _check(load().ffn_sparse_step(ctypes.byref(self.cfg), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY), _ptr(self.Y3),
+                                      _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _stream()))
+        return self.Y3, self.dX, self.dW1, self.dW2
+
+    def saved(self):
+        """Views of the intermediates the step leaves in its workspace (Alg. 2 line 1 and friends)."""
+        T, D, F, L = self.T, self.D, self.F, self.layout
+
+        def view(off, shape, dtype):
+            n = 1
+            for s in shape:
+                n *= s
+            nbytes = n * (2 if dtype == torch.bfloat16 else 1)
+            return self.ws[off:off + nbytes].view(dtype).view(shape)
+
+        return dict(w1_vals=view(L["w1_vals"], (F, D // 2), torch.bfloat16), w1_meta=view(L["w1_meta"], (F, D // 8), torch.uint8),
+                    w2t_vals=view(L["w2t_vals"], (F, D // 2), torch.bfloat16), w2t_meta=view(L["w2t_meta"], (F, D // 8), torch.uint8),
+                    y1=view(L["y1"], (T, F), torch.bfloat16), y2_vals=view(L["y2_vals"], (T, F // 4), torch.bfloat16),
+                    y2_meta=view(L["y2_meta"], (T, F // 16), torch.uint8), colidx=view(L["colidx"], (T // 64, F // 8, 4), torch.uint8),
+                    dy2=view(L["dy2"], (T, F), torch.bfloat16), dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16))
+
+
+def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD):
+    T, D = X.shape
+    F = W1.shape[0]
+    step = FfnStep(T, D, F, mode, X.device)
+    out = step(X, W1, W2, b1, dY)
+    return out, step

@@ -1,0 +1,248 @@
+// extern "C" boundary of the sparsified-FFN library: argument checks, workspace carving, and the
+// order of kernel launches of Alg. 1 / Alg. 2 (paper Section 3).  No allocation, no synchronisation.
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/sparseffn.h"
+#include "kernels.hpp"
+
+using namespace sffn;
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+int fail(int code, const char* fmt, const char* a = "") {
+    snprintf(g_err, sizeof(g_err), fmt, a);
+    return code;
+}
+int hipfail(hipError_t e, const char* where) {
+    snprintf(g_err, sizeof(g_err), "%s: %s", where, hipGetErrorString(e));
+    return SFFN_EHIP;
+}
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool mult64(int64_t v) { return v > 0 && (v % 64) == 0; }
+inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline bool fits_int(int64_t v) { return v < ((int64_t)1 << 31); }
+
+#define REQUIRE(cond, code, msg) do { if (!(cond)) return fail(code, "%s", msg); } while (0)
+#define LAUNCH(expr, where) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return hipfail(e_, where); } while (0)
+
+struct FullLayout {
+    sffn_ws_layout pub;
+    size_t w1t, xt, dyt, a24_vals, a24_meta, at, total;
+};
+
+bool make_layout(const sffn_cfg* c, FullLayout* L) {
+    if (!c || !mult64(c->T) || !mult64(c->D) || !mult64(c->F)) return false;
+    const size_t T = c->T, D = c->D, F = c->F;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
+    L->pub.w1_vals = take(F * D);          L->pub.w1_meta = take(F * D / 8);
+    L->pub.w2t_vals = take(F * D);         L->pub.w2t_meta = take(F * D / 8);
+    L->pub.y1 = take(T * F * 2);
+    L->pub.y2_vals = take(T * F / 2);      L->pub.y2_meta = take(T * F / 16);   L->pub.colidx = take(T / 64 * (F / 8) * 4);
+    L->pub.dy2 = take(T * F * 2);
+    L->pub.dy1_vals = take(T * F / 2);
+    L->w1t = take(D * F * 2);
+    L->xt = take(D * T * 2);
+    L->dyt = take(D * T * 2);
+    L->a24_vals = take(T * F);             L->a24_meta = take(T * F / 8);
+    L->at = take(F * T * 2);
+    L->total = off;
+    L->pub.total = off;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sffn_version(void) { return 100; }
+const char* sffn_last_error(void) { return g_err; }
+
+size_t sffn_workspace_bytes(const sffn_cfg* cfg) {
+    FullLayout L;
+    return make_layout(cfg, &L) ? L.total : 0;
+}
+
+int sffn_workspace_layout(const sffn_cfg* cfg, sffn_ws_layout* out) {
+    FullLayout L;
+    REQUIRE(out != nullptr, SFFN_EINVAL, "sffn_workspace_layout: out is null");
+    REQUIRE(make_layout(cfg, &L), SFFN_EINVAL, "sffn_workspace_layout: T, D, F must be positive multiples of 64");
+    *out = L.pub;
+    return SFFN_OK;
+}
+
+size_t sffn_vnm_spmm_workspace_bytes(int64_t T, int64_t N, int64_t Kfull, int w_kmajor) {
+    if (!mult64(T) || !mult64(N) || !mult64(Kfull)) return 0;
+    return up256((size_t)T * Kfull) + up256((size_t)T * Kfull / 8) + (w_kmajor ? up256((size_t)N * Kfull * 2) : 0);
+}
+
+size_t sffn_vnm_wgrad_workspace_bytes(int64_t T, int64_t F, int64_t N) {
+    if (!mult64(T) || !mult64(N) || !mult64(F)) return 0;
+    return up256((size_t)F * T * 2) + up256((size_t)N * T * 2);
+}
+
+int prune24_compress(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
+                     uint8_t* meta, void* stream) {
+    REQUIRE(src && vals && meta, SFFN_EINVAL, "prune24_compress: null pointer");
+    REQUIRE(mult64(R) && mult64(K), SFFN_EINVAL, "prune24_compress: R and K must be positive multiples of 64");
+    REQUIRE(ld >= (trans ? R : K) && ld % 8 == 0, SFFN_EINVAL, "prune24_compress: ld too small or not a multiple of 8");
+    REQUIRE(mode == SFFN_MODE_HARD || mode == SFFN_MODE_SOFT, SFFN_EINVAL, "prune24_compress: unknown mode");
+    REQUIRE(trans == 0 || trans == 1, SFFN_EINVAL, "prune24_compress: trans must be 0 or 1");
+    REQUIRE(aligned16(src) && aligned16(vals) && aligned16(meta), SFFN_EINVAL, "prune24_compress: pointers must be 16-byte aligned");
+    REQUIRE(fits_int(R) && fits_int(K), SFFN_EUNSUPPORTED, "prune24_compress: dimension above 2^31");
+    LAUNCH(launch_prune24(src, R, K, ld, trans, mode, vals, meta, (hipStream_t)stream), "prune24_compress");
+    return SFFN_OK;
+}
+
+int sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, int V, int M, uint16_t* vals, uint8_t* meta,
+                        uint8_t* colidx, void* stream) {
+    REQUIRE(y1 && vals && meta && colidx, SFFN_EINVAL, "sqrelu_vnm_compress: null pointer");
+    REQUIRE(mult64(T) && mult64(F), SFFN_EINVAL, "sqrelu_vnm_compress: T and F must be positive multiples of 64");
+    REQUIRE(V == 64 && M == 8, SFFN_EUNSUPPORTED, "sqrelu_vnm_compress: only V=64, M=8 is built");
+    REQUIRE(aligned16(y1) && aligned16(vals) && aligned16(meta) && aligned16(colidx), SFFN_EINVAL,
+            "sqrelu_vnm_compress: pointers must be 16-byte aligned");
+    REQUIRE(fits_int(T) && fits_int(F) && T / 64 < 65536, SFFN_EUNSUPPORTED, "sqrelu_vnm_compress: T too large");
+    LAUNCH(launch_sqrelu_vnm_compress(y1, T, F, vals, meta, colidx, (hipStream_t)stream), "sqrelu_vnm_compress");
+    return SFFN_OK;
+}
+
+static int spmm24_common(const char* name, const uint16_t* X, const uint16_t* w_vals, const uint8_t* w_meta, const float* bias,
+                         int64_t T, int64_t N, int64_t K, uint16_t* out, void* stream) {
+    REQUIRE(X && w_vals && w_meta && out, SFFN_EINVAL, "spmm24: null pointer");
+    REQUIRE(mult64(T) && mult64(N) && mult64(K), SFFN_EINVAL, "spmm24: T, N, K must be positive multiples of 64");
+    REQUIRE(aligned16(X) && aligned16(w_vals) && aligned16(w_meta) && aligned16(out) && aligned16(bias), SFFN_EINVAL,
+            "spmm24: pointers must be 16-byte aligned");
+    REQUIRE(fits_int(T) && fits_int(N) && fits_int(K), SFFN_EUNSUPPORTED, "spmm24: dimension above 2^31");
+    LAUNCH(launch_gemm_nt(1, w_vals, w_meta, X, bias, N, T, K, 1, out, N, (hipStream_t)stream), name);
+    return SFFN_OK;
+}
+
+int spmm24_fwd(const uint16_t* X, const uint16_t* w_vals, const uint8_t* w_meta, const float* bias, int64_t T, int64_t N,
+               int64_t K, uint16_t* out, void* stream) {
+    return spmm24_common("spmm24_fwd", X, w_vals, w_meta, bias, T, N, K, out, stream);
+}
+
+int spmm24_dgrad(const uint16_t* dY, const uint16_t* wt_vals, const uint8_t* wt_meta, int64_t T, int64_t N, int64_t K,
+                 uint16_t* out, void* stream) {
+    return spmm24_common("spmm24_dgrad", dY, wt_vals, wt_meta, nullptr, T, N, K, out, stream);
+}
+
+int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_colidx, const uint16_t* Wd, int64_t ldw,
+             int w_kmajor, int64_t T, int64_t N, int64_t Kfull, int V, int M, uint16_t* out, void* workspace,
+             size_t ws_bytes, void* stream) {
+    REQUIRE(a_vals && a_meta && a_colidx && Wd && out, SFFN_EINVAL, "vnm_spmm: null pointer");
+    REQUIRE(mult64(T) && mult64(N) && mult64(Kfull), SFFN_EINVAL, "vnm_spmm: T, N, Kfull must be positive multiples of 64");
+    REQUIRE(V == 64 && M == 8, SFFN_EUNSUPPORTED, "vnm_spmm: only V=64, M=8 is built");
+    REQUIRE(w_kmajor == 0 || w_kmajor == 1, SFFN_EINVAL, "vnm_spmm: w_kmajor must be 0 or 1");
+    REQUIRE(ldw >= (w_kmajor ? N : Kfull) && ldw % 8 == 0, SFFN_EINVAL, "vnm_spmm: ldw too small or not a multiple of 8");
+    REQUIRE(w_kmajor == 1 || ldw == Kfull, SFFN_EUNSUPPORTED, "vnm_spmm: a padded row stride needs w_kmajor=1");
+    REQUIRE(aligned16(a_vals) && aligned16(a_meta) && aligned16(a_colidx) && aligned16(Wd) && aligned16(out) && aligned16(workspace),
+            SFFN_EINVAL, "vnm_spmm: pointers must be 16-byte aligned");
+    REQUIRE(fits_int(T) && fits_int(N) && fits_int(Kfull) && T < 65536 * 64, SFFN_EUNSUPPORTED, "vnm_spmm: dimension too large");
+    REQUIRE(workspace && ws_bytes >= sffn_vnm_spmm_workspace_bytes(T, N, Kfull, w_kmajor), SFFN_EWORKSPACE,
+            "vnm_spmm: workspace missing or too small");
+    hipStream_t s = (hipStream_t)stream;
+    unsigned char* ws = (unsigned char*)workspace;
+    uint16_t* v24 = (uint16_t*)ws;
+    uint8_t* m24 = ws + up256((size_t)T * Kfull);
+    const uint16_t* W = Wd;
+    LAUNCH(launch_vnm_to_24(a_vals, a_meta, a_colidx, T, Kfull, v24, m24, s), "vnm_spmm/to24");
+    if (w_kmajor) {
+        uint16_t* wt = (uint16_t*)(m24 + up256((size_t)T * Kfull / 8));
+        LAUNCH(launch_transpose(Wd, Kfull, N, ldw, wt, s), "vnm_spmm/transpose");
+        W = wt;
+    }
+    LAUNCH(launch_gemm_nt(1, v24, m24, W, nullptr, T, N, Kfull, 0, out, N, s), "vnm_spmm/gemm");
+    return SFFN_OK;
+}
+
+int dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
+                int V, int M, uint16_t* dvals, void* stream) {
+    REQUIRE(dy2 && y1 && meta && colidx && dvals, SFFN_EINVAL, "dsqrelu_vnm: null pointer");
+    REQUIRE(mult64(T) && mult64(F), SFFN_EINVAL, "dsqrelu_vnm: T and F must be positive multiples of 64");
+    REQUIRE(V == 64 && M == 8, SFFN_EUNSUPPORTED, "dsqrelu_vnm: only V=64, M=8 is built");
+    REQUIRE(aligned16(dy2) && aligned16(y1) && aligned16(meta) && aligned16(colidx) && aligned16(dvals), SFFN_EINVAL,
+            "dsqrelu_vnm: pointers must be 16-byte aligned");
+    REQUIRE(fits_int(T) && fits_int(F) && T < 65536, SFFN_EUNSUPPORTED, "dsqrelu_vnm: T must be below 65536");
+    LAUNCH(launch_dsqrelu_vnm(dy2, y1, meta, colidx, T, F, dvals, (hipStream_t)stream), "dsqrelu_vnm");
+    return SFFN_OK;
+}
+
+int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_colidx, const uint16_t* G, int64_t T,
+              int64_t F, int64_t N, int V, int M, int out_f_major, uint16_t* out, void* workspace, size_t ws_bytes,
+              void* stream) {
+    REQUIRE(a_vals && a_meta && a_colidx && G && out, SFFN_EINVAL, "vnm_wgrad: null pointer");
+    REQUIRE(mult64(T) && mult64(N) && mult64(F), SFFN_EINVAL, "vnm_wgrad: T, F, N must be positive multiples of 64");
+    REQUIRE(V == 64 && M == 8, SFFN_EUNSUPPORTED, "vnm_wgrad: only V=64, M=8 is built");
+    REQUIRE(out_f_major == 0 || out_f_major == 1, SFFN_EINVAL, "vnm_wgrad: out_f_major must be 0 or 1");
+    REQUIRE(aligned16(a_vals) && aligned16(a_meta) && aligned16(a_colidx) && aligned16(G) && aligned16(out) && aligned16(workspace),
+            SFFN_EINVAL, "vnm_wgrad: pointers must be 16-byte aligned");
+    REQUIRE(fits_int(T) && fits_int(N) && fits_int(F) && T < 65536 * 64, SFFN_EUNSUPPORTED, "vnm_wgrad: dimension too large");
+    REQUIRE(workspace && ws_bytes >= sffn_vnm_wgrad_workspace_bytes(T, F, N), SFFN_EWORKSPACE,
+            "vnm_wgrad: workspace missing or too small");
+    hipStream_t s = (hipStream_t)stream;
+    uint16_t* at = (uint16_t*)workspace;
+    uint16_t* gt = (uint16_t*)((unsigned char*)workspace + up256((size_t)F * T * 2));
+    LAUNCH(launch_vnm_expand_t(a_vals, a_meta, a_colidx, T, F, at, s), "vnm_wgrad/expand");
+    LAUNCH(launch_transpose(G, T, N, N, gt, s), "vnm_wgrad/transpose");
+    // C[i=f][j=n]; out_f_major: out[f*N + n] (j contiguous) else out[n*F + f] (i contiguous)
+    if (out_f_major) LAUNCH(launch_gemm_nt(0, at, nullptr, gt, nullptr, F, N, T, 0, out, N, s), "vnm_wgrad/gemm");
+    else             LAUNCH(launch_gemm_nt(0, at, nullptr, gt, nullptr, F, N, T, 1, out, F, s), "vnm_wgrad/gemm");
+    return SFFN_OK;
+}
+
+int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, const uint16_t* W2, const float* b1,
+                    const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace,
+                    size_t ws_bytes, void* stream) {
+    REQUIRE(cfg && X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_sparse_step: null pointer");
+    FullLayout L;
+    REQUIRE(make_layout(cfg, &L), SFFN_EINVAL, "ffn_sparse_step: T, D, F must be positive multiples of 64");
+    REQUIRE(cfg->V == 64 && cfg->M == 8, SFFN_EUNSUPPORTED, "ffn_sparse_step: only V=64, M=8 is built");
+    REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_sparse_step: unknown mode");
+    REQUIRE(aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(b1) && aligned16(dY) && aligned16(Y3) && aligned16(dX) &&
+                aligned16(dW1) && aligned16(dW2) && aligned16(workspace),
+            SFFN_EINVAL, "ffn_sparse_step: pointers must be 16-byte aligned");
+    REQUIRE(cfg->T < 65536 && fits_int(cfg->F) && fits_int(cfg->D), SFFN_EUNSUPPORTED, "ffn_sparse_step: T must be below 65536");
+    REQUIRE(workspace && ws_bytes >= L.total, SFFN_EWORKSPACE, "ffn_sparse_step: workspace missing or too small");
+
+    const int64_t T = cfg->T, D = cfg->D, F = cfg->F;
+    hipStream_t s = (hipStream_t)stream;
+    unsigned char* ws = (unsigned char*)workspace;
+    uint16_t* w1v = (uint16_t*)(ws + L.pub.w1_vals);    uint8_t* w1m = ws + L.pub.w1_meta;
+    uint16_t* w2v = (uint16_t*)(ws + L.pub.w2t_vals);   uint8_t* w2m = ws + L.pub.w2t_meta;
+    uint16_t* y1 = (uint16_t*)(ws + L.pub.y1);
+    uint16_t* y2v = (uint16_t*)(ws + L.pub.y2_vals);    uint8_t* y2m = ws + L.pub.y2_meta;   uint8_t* cix = ws + L.pub.colidx;
+    uint16_t* dy2 = (uint16_t*)(ws + L.pub.dy2);
+    uint16_t* dy1v = (uint16_t*)(ws + L.pub.dy1_vals);
+    uint16_t* w1t = (uint16_t*)(ws + L.w1t);
+    uint16_t* xt = (uint16_t*)(ws + L.xt);
+    uint16_t* dyt = (uint16_t*)(ws + L.dyt);
+    uint16_t* a24v = (uint16_t*)(ws + L.a24_vals);      uint8_t* a24m = ws + L.a24_meta;
+    uint16_t* at = (uint16_t*)(ws + L.at);
+
+    // ---- Alg. 1 -------------------------------------------------------------------------------
+    LAUNCH(launch_prune24(W1, F, D, D, 0, cfg->mode, w1v, w1m, s), "step/prune24(W1)");
+    LAUNCH(launch_gemm_nt(1, w1v, w1m, X, b1, F, T, D, 1, y1, F, s), "step/y1");                 // eq. (1)
+    LAUNCH(launch_sqrelu_vnm_compress(y1, T, F, y2v, y2m, cix, s), "step/sqrelu_vnm_compress");   // eq. (2) + V:N:M
+    LAUNCH(launch_vnm_to_24(y2v, y2m, cix, T, F, a24v, a24m, s), "step/y2->2:4");
+    LAUNCH(launch_gemm_nt(1, a24v, a24m, W2, nullptr, T, D, F, 0, Y3, D, s), "step/y3");          // eq. (3)
+    // ---- Alg. 2 -------------------------------------------------------------------------------
+    LAUNCH(launch_prune24(W2, F, D, F, 1, cfg->mode, w2v, w2m, s), "step/prune24(W2.T)");
+    LAUNCH(launch_gemm_nt(1, w2v, w2m, dY, nullptr, F, T, D, 1, dy2, F, s), "step/dy2");          // eq. (4)
+    LAUNCH(launch_vnm_expand_t(y2v, y2m, cix, T, F, at, s), "step/y2 expand");
+    LAUNCH(launch_transpose(dY, T, D, D, dyt, s), "step/dY.T");
+    LAUNCH(launch_gemm_nt(0, at, nullptr, dyt, nullptr, F, D, T, 1, dW2, F, s), "step/dW2");      // eq. (5)
+    LAUNCH(launch_dsqrelu_vnm(dy2, y1, y2m, cix, T, F, dy1v, s), "step/dsqrelu_vnm");             // eq. (6)
+    LAUNCH(launch_vnm_to_24(dy1v, y2m, cix, T, F, a24v, a24m, s), "step/dy1->2:4");
+    LAUNCH(launch_transpose(W1, F, D, D, w1t, s), "step/W1.T");
+    LAUNCH(launch_gemm_nt(1, a24v, a24m, w1t, nullptr, T, D, F, 0, dX, D, s), "step/dX");         // eq. (7)
+    LAUNCH(launch_vnm_expand_t(dy1v, y2m, cix, T, F, at, s), "step/dy1 expand");
+    LAUNCH(launch_transpose(X, T, D, D, xt, s), "step/X.T");
+    LAUNCH(launch_gemm_nt(0, at, nullptr, xt, nullptr, F, D, T, 0, dW1, D, s), "step/dW1");       // eq. (8)
+    return SFFN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,27 @@
+// Host-side launchers of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sffn {
+
+hipError_t launch_prune24(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
+                          uint8_t* meta, hipStream_t stream);
+hipError_t launch_sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, uint16_t* vals, uint8_t* meta,
+                                      uint8_t* colidx, hipStream_t s);
+hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, const uint8_t* colidx,
+                              int64_t T, int64_t F, uint16_t* dvals, hipStream_t s);
+hipError_t launch_vnm_to_24(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
+                            uint16_t* vals24, uint8_t* meta24, hipStream_t s);
+hipError_t launch_vnm_expand_t(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
+                               uint16_t* out, hipStream_t s);
+hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld, uint16_t* out, hipStream_t s);
+
+// C[i, j] = sum_k A[i, k] * B[j, k]  (both operands K-contiguous).
+//   sparse_a: A given as 2:4 packed (a_vals [Ra, K/2], a_meta [Ra, K/8]) and multiplied on the
+//             structured-sparse matrix cores; else a_vals is a dense [Ra, K] matrix.
+//   out_i_contig: 1 -> out[j * ldo + i] (+ bias[i]);  0 -> out[i * ldo + j].
+hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
+                          int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
+
+}  // namespace sffn

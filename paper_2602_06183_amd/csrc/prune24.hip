@@ -1,0 +1,99 @@
+// prune24_compress: per-iteration 2:4 prune-and-pack of a weight matrix (paper Section 2.2 and the
+// "sparsify24" calls of Alg. 1 line 4 / Alg. 2 line 2).  HBM-bound element-wise scan: every input
+// element is read once (16-byte loads), 0.5 element of values and 1/16 byte of metadata are written.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace sffn {
+
+// ---- rows are K-contiguous: one thread per 8 consecutive elements (two groups) -----------------
+template <bool SOFT, bool FLAT>
+__global__ void __launch_bounds__(256) prune24_rows_kernel(const uint16_t* __restrict__ src, int64_t nchunks, int cpr,
+                                                          int64_t ld, uint16_t* __restrict__ vals,
+                                                          uint8_t* __restrict__ meta) {
+    constexpr int UNROLL = 4;
+    const int64_t base = (int64_t)blockIdx.x * (256 * UNROLL) + threadIdx.x;
+    uint4 w[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t c = base + u * 256;
+        if (c < nchunks) {
+            int64_t off;
+            if (FLAT) off = c * 8;
+            else { const int64_t r = c / cpr; off = r * ld + (c - r * cpr) * 8; }
+            w[u] = *reinterpret_cast<const uint4*>(src + off);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int64_t c = base + u * 256;
+        if (c < nchunks) {
+            uint32_t n0, n1;
+            const uint32_t o0 = select24<SOFT>(w[u].x & 0xFFFFu, w[u].x >> 16, w[u].y & 0xFFFFu, w[u].y >> 16, n0);
+            const uint32_t o1 = select24<SOFT>(w[u].z & 0xFFFFu, w[u].z >> 16, w[u].w & 0xFFFFu, w[u].w >> 16, n1);
+            *reinterpret_cast<uint2*>(vals + c * 4) = make_uint2(o0, o1);
+            meta[c] = (uint8_t)(n0 | (n1 << 4));
+        }
+    }
+}
+
+// ---- groups run along the strided axis: S[r,k] = src[k*ld + r] ---------------------------------
+// A workgroup takes 64 logical rows x 128 k: the 128 x 64 source tile goes through LDS so that
+// both the HBM reads (128 B row segments) and the packed writes (32 B per thread, 128 B per row)
+// stay contiguous.
+template <bool SOFT>
+__global__ void __launch_bounds__(256) prune24_cols_kernel(const uint16_t* __restrict__ src, int64_t R, int K, int64_t ld,
+                                                          uint16_t* __restrict__ vals, uint8_t* __restrict__ meta) {
+    constexpr int TK = 128, TR = 64, PITCH = TR + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t tile[TK * PITCH];
+    const int64_t r0 = (int64_t)blockIdx.x * TR;
+    const int k0 = blockIdx.y * TK;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int kk = tid / 8 + 32 * i, seg = tid % 8;
+        uint4 w = make_uint4(0, 0, 0, 0);
+        if (k0 + kk < K) w = *reinterpret_cast<const uint4*>(src + (int64_t)(k0 + kk) * ld + r0 + seg * 8);
+        *reinterpret_cast<uint4*>(&tile[kk * PITCH + seg * 8]) = w;
+    }
+    __syncthreads();
+    const int rr = tid % 64, q = tid / 64;
+    if (k0 + 32 * q >= K) return;
+    uint32_t ov[8], mbytes = 0;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+        const uint16_t* p = &tile[(32 * q + 4 * g) * PITCH + rr];
+        uint32_t nib;
+        ov[g] = select24<SOFT>(p[0], p[PITCH], p[2 * PITCH], p[3 * PITCH], nib);
+        mbytes |= nib << (4 * g);
+    }
+    const int64_t r = r0 + rr;
+    uint16_t* vo = vals + r * (K / 2) + (k0 + 32 * q) / 2;
+    *reinterpret_cast<uint4*>(vo) = make_uint4(ov[0], ov[1], ov[2], ov[3]);
+    *reinterpret_cast<uint4*>(vo + 8) = make_uint4(ov[4], ov[5], ov[6], ov[7]);
+    *reinterpret_cast<uint32_t*>(meta + r * (K / 8) + (k0 + 32 * q) / 8) = mbytes;
+}
+
+hipError_t launch_prune24(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
+                          uint8_t* meta, hipStream_t stream) {
+    if (!trans) {
+        const int64_t nchunks = R * (K / 8);
+        const unsigned grid = (unsigned)((nchunks + 1023) / 1024);
+        const int cpr = (int)(K / 8);
+        const bool flat = (ld == K);
+        if (mode == 0) {
+            if (flat) hipLaunchKernelGGL((prune24_rows_kernel<false, true>), dim3(grid), dim3(256), 0, stream, src, nchunks, cpr, ld, vals, meta);
+            else      hipLaunchKernelGGL((prune24_rows_kernel<false, false>), dim3(grid), dim3(256), 0, stream, src, nchunks, cpr, ld, vals, meta);
+        } else {
+            if (flat) hipLaunchKernelGGL((prune24_rows_kernel<true, true>), dim3(grid), dim3(256), 0, stream, src, nchunks, cpr, ld, vals, meta);
+            else      hipLaunchKernelGGL((prune24_rows_kernel<true, false>), dim3(grid), dim3(256), 0, stream, src, nchunks, cpr, ld, vals, meta);
+        }
+    } else {
+        dim3 grid((unsigned)(R / 64), (unsigned)((K + 127) / 128));
+        if (mode == 0) hipLaunchKernelGGL((prune24_cols_kernel<false>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta);
+        else           hipLaunchKernelGGL((prune24_cols_kernel<true>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace sffn

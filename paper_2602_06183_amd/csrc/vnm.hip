@@ -1,0 +1,241 @@
+// V:N:M (V=64, N=2, M=8) kernels: SquaredReLU + on-the-fly compression of the hidden activation
+// (paper eq. (2), Section 2.3, Alg. 1 lines 5-6), eq. (6) on the kept slots (Alg. 2 line 4), and the
+// layout helpers the GEMMs consume (re-expression as plain 2:4 over all columns, dense transposed
+// expansion, bf16 transpose).  All of them are HBM-bound scans.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace sffn {
+
+__device__ __forceinline__ uint32_t pick16(const uint32_t (&w)[4], uint32_t c) {
+    const uint32_t d = c >> 1;
+    const uint32_t lo = (d == 0) ? w[0] : (d == 1) ? w[1] : (d == 2) ? w[2] : w[3];
+    return (c & 1u) ? (lo >> 16) : (lo & 0xFFFFu);
+}
+
+__device__ __forceinline__ uint32_t sqrelu_pair(uint32_t w) {
+    const float a = bf2f(w & 0xFFFFu), b = bf2f(w >> 16);
+    const float ra = a > 0.0f ? a : 0.0f, rb = b > 0.0f ? b : 0.0f;
+    return f2bf(ra * ra) | (f2bf(rb * rb) << 16);
+}
+
+// One workgroup = 64 rows (one V block) x 64 column blocks (512 columns).  Wave w holds rows
+// 16w..16w+15 of every block in registers as y2; the column scores are a strict left-to-right
+// fp32 sum over the 64 rows, so the four waves add their rows one after the other, handing the
+// running sums over through LDS.  Lane = column block, so every HBM access of a wave is one
+// contiguous 1 KB (loads), 256 B (values) or 32 B (metadata) run.
+__global__ void __launch_bounds__(256) sqrelu_vnm_compress_kernel(const uint16_t* __restrict__ y1, int64_t F, int nblk,
+                                                                 uint16_t* __restrict__ vals, uint8_t* __restrict__ meta,
+                                                                 uint8_t* __restrict__ colidx) {
+    __shared__ float s_score[8][64];
+    __shared__ uint32_t s_col[64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int blk = blockIdx.x * 64 + lane;
+    const bool active = blk < nblk;
+    const int64_t tb = blockIdx.y;
+    const int64_t row0 = tb * 64 + wave * 16;
+
+    uint32_t y2[16][4];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        uint4 w = make_uint4(0, 0, 0, 0);
+        if (active) w = *reinterpret_cast<const uint4*>(y1 + (row0 + i) * F + (int64_t)blk * 8);
+        y2[i][0] = sqrelu_pair(w.x); y2[i][1] = sqrelu_pair(w.y);
+        y2[i][2] = sqrelu_pair(w.z); y2[i][3] = sqrelu_pair(w.w);
+    }
+
+    // ordered score chain: wave 0 rows 0-15, wave 1 rows 16-31, ...
+    for (int turn = 0; turn < 4; ++turn) {
+        if (wave == turn) {
+            float sc[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) sc[c] = (turn == 0) ? 0.0f : s_score[c][lane];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    sc[2 * d] = sc[2 * d] + bf2f(y2[i][d] & 0xFFFFu);
+                    sc[2 * d + 1] = sc[2 * d + 1] + bf2f(y2[i][d] >> 16);
+                }
+            }
+            if (turn < 3) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) s_score[c][lane] = sc[c];
+            } else {
+                // four largest scores, ties to the lower column; offsets stored ascending
+                uint32_t packed = 0, n = 0;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    int rank = 0;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        if (j < c) rank += (sc[j] >= sc[c]);
+                        else if (j > c) rank += (sc[j] > sc[c]);
+                    }
+                    if (rank < 4) { packed |= (uint32_t)c << (8 * n); ++n; }
+                }
+                s_col[lane] = packed;
+                if (active) *reinterpret_cast<uint32_t*>(colidx + (tb * nblk + blk) * 4) = packed;
+            }
+        }
+        __syncthreads();
+    }
+
+    const uint32_t cw = s_col[lane];
+    const uint32_t c0 = cw & 0xFFu, c1 = (cw >> 8) & 0xFFu, c2 = (cw >> 16) & 0xFFu, c3 = cw >> 24;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        uint32_t nib;
+        const uint32_t v = select24<false>(pick16(y2[i], c0), pick16(y2[i], c1), pick16(y2[i], c2), pick16(y2[i], c3), nib);
+        const uint32_t other = (uint32_t)__shfl_xor((int)nib, 1, 64);
+        if (active) {
+            const int64_t row = row0 + i;
+            *reinterpret_cast<uint32_t*>(vals + row * (F / 4) + (int64_t)blk * 2) = v;
+            if ((lane & 1) == 0) meta[row * (F / 16) + (blk >> 1)] = (uint8_t)(nib | (other << 4));
+        }
+    }
+}
+
+// eq. (6) evaluated only where y2 was kept.  One thread per (row, column block).
+__global__ void __launch_bounds__(256) dsqrelu_vnm_kernel(const uint16_t* __restrict__ dy2, const uint16_t* __restrict__ y1,
+                                                         const uint8_t* __restrict__ meta, const uint8_t* __restrict__ colidx,
+                                                         int64_t F, int nblk, uint16_t* __restrict__ dvals) {
+    const int blk = blockIdx.x * 256 + threadIdx.x;
+    if (blk >= nblk) return;
+    const int64_t t = blockIdx.y;
+    const uint32_t cw = *reinterpret_cast<const uint32_t*>(colidx + ((t >> 6) * nblk + blk) * 4);
+    const uint32_t nib = (meta[t * (F / 16) + (blk >> 1)] >> (4 * (blk & 1))) & 0xFu;
+    const uint32_t o0 = (cw >> (8 * (nib & 3u))) & 0xFFu, o1 = (cw >> (8 * (nib >> 2))) & 0xFFu;
+    const uint4 d4 = *reinterpret_cast<const uint4*>(dy2 + t * F + (int64_t)blk * 8);
+    const uint4 y4 = *reinterpret_cast<const uint4*>(y1 + t * F + (int64_t)blk * 8);
+    const uint32_t dw[4] = {d4.x, d4.y, d4.z, d4.w}, yw[4] = {y4.x, y4.y, y4.z, y4.w};
+    const float ya = bf2f(pick16(yw, o0)), yb = bf2f(pick16(yw, o1));
+    const float ga = 2.0f * bf2f(pick16(dw, o0)) * (ya > 0.0f ? ya : 0.0f);
+    const float gb = 2.0f * bf2f(pick16(dw, o1)) * (yb > 0.0f ? yb : 0.0f);
+    *reinterpret_cast<uint32_t*>(dvals + t * (F / 4) + (int64_t)blk * 2) = f2bf(ga) | (f2bf(gb) << 16);
+}
+
+// Two survivors per 8 columns leave at most two per aligned group of four, so a V:2:8 matrix is
+// also a plain 2:4 matrix over all F columns.  This writes that view: vals24 [T, F/2], meta24
+// [T, F/8] in the 2:4 packed format (empty slots are +0 at unused positions).
+__global__ void __launch_bounds__(256) vnm_to_24_kernel(const uint16_t* __restrict__ vals, const uint8_t* __restrict__ meta,
+                                                       const uint8_t* __restrict__ colidx, int64_t F, int nblk,
+                                                       uint16_t* __restrict__ vals24, uint8_t* __restrict__ meta24) {
+    const int blk = blockIdx.x * 256 + threadIdx.x;
+    if (blk >= nblk) return;
+    const int64_t t = blockIdx.y;
+    const uint32_t cw = *reinterpret_cast<const uint32_t*>(colidx + ((t >> 6) * nblk + blk) * 4);
+    const uint32_t nib = (meta[t * (F / 16) + (blk >> 1)] >> (4 * (blk & 1))) & 0xFu;
+    const uint32_t o0 = (cw >> (8 * (nib & 3u))) & 0xFFu, o1 = (cw >> (8 * (nib >> 2))) & 0xFFu;   // o0 < o1
+    const uint32_t v = *reinterpret_cast<const uint32_t*>(vals + t * (F / 4) + (int64_t)blk * 2);
+    const uint32_t v0 = v & 0xFFFFu, v1 = v >> 16;
+    uint32_t a, na, b, nb;            // low group (columns 0-3) and high group (columns 4-7)
+    if (o1 < 4) {
+        a = v; na = o0 | (o1 << 2); b = 0; nb = 0x4;
+    } else if (o0 >= 4) {
+        a = 0; na = 0x4; b = v; nb = (o0 - 4) | ((o1 - 4) << 2);
+    } else {
+        if (o0 < 3) { a = v0; na = o0 | (3u << 2); } else { a = v0 << 16; na = 0u | (3u << 2); }
+        const uint32_t q = o1 - 4;
+        if (q > 0) { b = v1 << 16; nb = 0u | (q << 2); } else { b = v1; nb = 0u | (1u << 2); }
+    }
+    *reinterpret_cast<uint2*>(vals24 + t * (F / 2) + (int64_t)blk * 4) = make_uint2(a, b);
+    meta24[t * (F / 8) + blk] = (uint8_t)(na | (nb << 4));
+}
+
+// Dense, transposed expansion AT[f, t] of a V:N:M matrix (K-contiguous operand for the
+// weight-gradient GEMMs).  One workgroup = 64 rows x 8 column blocks.
+__global__ void __launch_bounds__(256) vnm_expand_t_kernel(const uint16_t* __restrict__ vals, const uint8_t* __restrict__ meta,
+                                                          const uint8_t* __restrict__ colidx, int64_t T, int64_t F, int nblk,
+                                                          uint16_t* __restrict__ out) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64][64 + 8];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < 64 * 72 / 2; i += 256) reinterpret_cast<uint32_t*>(&tile[0][0])[i] = 0;
+    __syncthreads();
+    const int64_t tb = blockIdx.y;
+    const int b0 = blockIdx.x * 8;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int e = tid + 256 * i;           // 64 rows x 8 blocks
+        const int r = e >> 3, bl = e & 7, blk = b0 + bl;
+        const int64_t t = tb * 64 + r;
+        const uint32_t cw = *reinterpret_cast<const uint32_t*>(colidx + (tb * nblk + blk) * 4);
+        const uint32_t nib = (meta[t * (F / 16) + (blk >> 1)] >> (4 * (blk & 1))) & 0xFu;
+        const uint32_t o0 = (cw >> (8 * (nib & 3u))) & 0xFFu, o1 = (cw >> (8 * (nib >> 2))) & 0xFFu;
+        const uint32_t v = *reinterpret_cast<const uint32_t*>(vals + t * (F / 4) + (int64_t)blk * 2);
+        tile[bl * 8 + o0][r] = (uint16_t)(v & 0xFFFFu);
+        tile[bl * 8 + o1][r] = (uint16_t)(v >> 16);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int e = tid + 256 * i;           // 64 f rows x 8 segments of 8 tokens
+        const int fr = e >> 3, seg = e & 7;
+        *reinterpret_cast<uint4*>(out + ((int64_t)b0 * 8 + fr) * T + tb * 64 + seg * 8) =
+            *reinterpret_cast<const uint4*>(&tile[fr][seg * 8]);
+    }
+}
+
+// out[c, r] = in[r, c]; R, C multiples of 64.
+__global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* __restrict__ in, int64_t R, int64_t C, int64_t ld,
+                                                            uint16_t* __restrict__ out) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64][64 + 2];
+    const int tid = threadIdx.x;
+    const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int e = tid + 256 * i, rr = e >> 3, seg = e & 7;
+        const uint4 w = *reinterpret_cast<const uint4*>(in + (r0 + rr) * ld + c0 + seg * 8);
+        uint32_t* p = reinterpret_cast<uint32_t*>(&tile[rr][seg * 8]);
+        p[0] = w.x; p[1] = w.y; p[2] = w.z; p[3] = w.w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int e = tid + 256 * i, cc = e >> 3, seg = e & 7;
+        uint32_t o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = tile[seg * 8 + 2 * j][cc] | ((uint32_t)tile[seg * 8 + 2 * j + 1][cc] << 16);
+        *reinterpret_cast<uint4*>(out + (c0 + cc) * R + r0 + seg * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+hipError_t launch_sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, uint16_t* vals, uint8_t* meta, uint8_t* colidx,
+                                      hipStream_t s) {
+    const int nblk = (int)(F / 8);
+    dim3 grid((unsigned)((nblk + 63) / 64), (unsigned)(T / 64));
+    hipLaunchKernelGGL(sqrelu_vnm_compress_kernel, grid, dim3(256), 0, s, y1, F, nblk, vals, meta, colidx);
+    return hipGetLastError();
+}
+
+hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, const uint8_t* colidx, int64_t T,
+                              int64_t F, uint16_t* dvals, hipStream_t s) {
+    const int nblk = (int)(F / 8);
+    dim3 grid((unsigned)((nblk + 255) / 256), (unsigned)T);
+    hipLaunchKernelGGL(dsqrelu_vnm_kernel, grid, dim3(256), 0, s, dy2, y1, meta, colidx, F, nblk, dvals);
+    return hipGetLastError();
+}
+
+hipError_t launch_vnm_to_24(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
+                            uint16_t* vals24, uint8_t* meta24, hipStream_t s) {
+    const int nblk = (int)(F / 8);
+    dim3 grid((unsigned)((nblk + 255) / 256), (unsigned)T);
+    hipLaunchKernelGGL(vnm_to_24_kernel, grid, dim3(256), 0, s, vals, meta, colidx, F, nblk, vals24, meta24);
+    return hipGetLastError();
+}
+
+hipError_t launch_vnm_expand_t(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
+                               uint16_t* out, hipStream_t s) {
+    const int nblk = (int)(F / 8);
+    dim3 grid((unsigned)(nblk / 8), (unsigned)(T / 64));
+    hipLaunchKernelGGL(vnm_expand_t_kernel, grid, dim3(256), 0, s, vals, meta, colidx, T, F, nblk, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld, uint16_t* out, hipStream_t s) {
+    dim3 grid((unsigned)(C / 64), (unsigned)(R / 64));
+    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, in, R, C, ld, out);
+    return hipGetLastError();
+}
+
+}  // namespace sffn

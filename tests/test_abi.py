@@ -1,0 +1,73 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every symbol the header
+declares, and rejects bad arguments before enqueuing anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2602_06183_amd as sffn
+from paper_2602_06183_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sparseffn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined", "sizeof"})
+
+
+def test_library_exports_every_declared_symbol():
+    lib = sffn.load()
+    names = declared_symbols()
+    for must in ("prune24_compress", "sqrelu_vnm_compress", "spmm24_fwd", "spmm24_dgrad", "vnm_wgrad", "ffn_sparse_step",
+                 "vnm_spmm", "dsqrelu_vnm", "sffn_workspace_bytes", "sffn_workspace_layout"):
+        assert must in names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sffn.version() >= 100
+
+
+def test_workspace_queries():
+    assert sffn.workspace_bytes(512, 256, 1024) > 0
+    assert sffn.workspace_bytes(500, 256, 1024) == 0          # T not a multiple of 64
+    lay = sffn.workspace_layout(512, 256, 1024)
+    offs = [lay[k] for k in ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta", "y1", "y2_vals", "y2_meta", "colidx", "dy2", "dy1_vals")]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs) and lay["total"] == sffn.workspace_bytes(512, 256, 1024)
+    lib = sffn.load()
+    assert lib.sffn_vnm_spmm_workspace_bytes(64, 64, 64, 1) > lib.sffn_vnm_spmm_workspace_bytes(64, 64, 64, 0) > 0
+    assert lib.sffn_vnm_wgrad_workspace_bytes(64, 64, 63) == 0
+
+
+def test_bad_arguments_are_rejected_without_touching_the_gpu():
+    lib = sffn.load()
+    fake = ctypes.c_void_p(0x1000)        # 16-byte aligned, never dereferenced: every call below fails validation first
+    odd = ctypes.c_void_p(0x1008)
+    assert lib.prune24_compress(None, 64, 64, 64, 0, 0, fake, fake, None) == -1
+    assert lib.prune24_compress(fake, 64, 60, 64, 0, 0, fake, fake, None) == -1
+    assert lib.prune24_compress(fake, 64, 64, 32, 0, 0, fake, fake, None) == -1
+    assert lib.prune24_compress(fake, 64, 64, 64, 0, 7, fake, fake, None) == -1
+    assert lib.prune24_compress(odd, 64, 64, 64, 0, 0, fake, fake, None) == -1
+    assert b"aligned" in lib.sffn_last_error()
+    assert lib.sqrelu_vnm_compress(fake, 64, 64, 64, 16, fake, fake, fake, None) == -2      # M = 16 not built
+    assert lib.sqrelu_vnm_compress(fake, 63, 64, 64, 8, fake, fake, fake, None) == -1
+    assert lib.spmm24_fwd(fake, fake, fake, None, 64, 64, 65, fake, None) == -1
+    assert lib.spmm24_dgrad(fake, fake, None, 64, 64, 64, fake, None) == -1
+    assert lib.vnm_spmm(fake, fake, fake, fake, 64, 0, 64, 64, 64, 64, 8, fake, None, 0, None) == -3
+    assert lib.vnm_spmm(fake, fake, fake, fake, 64, 0, 64, 64, 64, 32, 8, fake, fake, 1 << 20, None) == -2
+    assert lib.dsqrelu_vnm(fake, fake, fake, fake, 64, 100, 64, 8, fake, None) == -1
+    assert lib.vnm_wgrad(fake, fake, fake, fake, 64, 64, 64, 64, 8, 0, fake, fake, 16, None) == -3
+    cfg = binding._Cfg(512, 256, 1024, 64, 8, 0, 0)
+    args = [fake] * 9
+    assert lib.ffn_sparse_step(ctypes.byref(cfg), *args, fake, 16, None) == -3
+    bad = binding._Cfg(512, 250, 1024, 64, 8, 0, 0)
+    assert lib.ffn_sparse_step(ctypes.byref(bad), *args, fake, 1 << 30, None) == -1
+    assert len(lib.sffn_last_error()) > 0
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "_HERE", str(tmp_path))
+    with pytest.raises(sffn.SffnError):
+        binding.load()

@@ -1,0 +1,208 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on identical seeded inputs.
+Packed values, metadata and column indices must match bit for bit; GEMM outputs within
+relative Frobenius 5e-3 and max elementwise 2e-2 * max|ref|."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_06183_amd as sffn
+from tests.util import to_dev, to_bits, assert_gemm_close
+from workload import make_ffn_inputs, bf16_bits_from_f32
+
+pytestmark = pytest.mark.gpu
+
+
+def rnd_bits(rng, shape, scale=1.0):
+    return bf16_bits_from_f32(rng.standard_normal(shape, dtype=np.float32) * np.float32(scale))
+
+
+def adversarial_rows(K):
+    """Rows of 2:4 corner cases: zero groups, equal magnitudes, +-0, opposite signs, subnormals, max finite."""
+    pats = [
+        [0x0000, 0x0000, 0x0000, 0x0000], [0x8000, 0x0000, 0x8000, 0x0000], [0x3F80, 0x3F80, 0x3F80, 0x3F80],
+        [0x3F80, 0xBF80, 0x3F80, 0xBF80], [0x0001, 0x8001, 0x0002, 0x0000], [0x7F7F, 0xFF7F, 0x7F7F, 0x0001],
+        [0x0000, 0x0000, 0x0000, 0x3F80], [0x4000, 0x3F80, 0x3F80, 0x4000], [0x3F80, 0x4000, 0x4000, 0x3F80],
+        [0x3FC0, 0x3F80, 0x3FC0, 0x3F80], [0x0080, 0x0081, 0x007F, 0x8080], [0x3F81, 0x3F80, 0xBF81, 0x3F7F],
+    ]
+    flat = np.array(pats, dtype=np.uint16).reshape(-1)
+    reps = (K + flat.size - 1) // flat.size
+    rows = [np.tile(np.roll(flat, 4 * s), reps)[:K] for s in range(len(pats))]
+    return np.stack(rows)
+
+
+@pytest.mark.parametrize("mode", [sffn.MODE_HARD, sffn.MODE_SOFT])
+@pytest.mark.parametrize("R,K", [(64, 64), (192, 320), (1024, 256), (448, 2048)])
+def test_prune24_rows(R, K, mode):
+    rng = np.random.default_rng(R * 7 + K)
+    W = rnd_bits(rng, (R, K), 0.02)
+    adv = adversarial_rows(K)
+    W[: adv.shape[0]] = adv
+    vals, meta = sffn.prune24_compress(to_dev(W), trans=False, mode=mode)
+    rv, rm = oracle.prune24_compress(W, mode)
+    assert np.array_equal(to_bits(meta), rm)
+    assert np.array_equal(to_bits(vals), rv)
+
+
+def test_prune24_rows_strided():
+    rng = np.random.default_rng(5)
+    big = rnd_bits(rng, (128, 384), 0.02)
+    view = to_dev(big)[:, 64:320]                 # ld = 384, K = 256, 16-byte aligned start
+    vals, meta = sffn.prune24_compress(view, trans=False, mode=sffn.MODE_SOFT)
+    rv, rm = oracle.prune24_compress(big[:, 64:320], sffn.MODE_SOFT)
+    assert np.array_equal(to_bits(meta), rm) and np.array_equal(to_bits(vals), rv)
+
+
+@pytest.mark.parametrize("mode", [sffn.MODE_HARD, sffn.MODE_SOFT])
+@pytest.mark.parametrize("R,K", [(64, 64), (192, 320), (1024, 256), (448, 2048)])
+def test_prune24_trans(R, K, mode):
+    """sparsify24(W2.T): groups run down the rows of the stored [K, R] matrix."""
+    rng = np.random.default_rng(R * 3 + K)
+    S = rnd_bits(rng, (R, K), 0.02)               # logical matrix
+    adv = adversarial_rows(K)
+    S[: adv.shape[0]] = adv
+    stored = np.ascontiguousarray(S.T)            # [K, R]
+    vals, meta = sffn.prune24_compress(to_dev(stored), trans=True, mode=mode)
+    rv, rm = oracle.prune24_compress(S, mode)
+    assert np.array_equal(to_bits(meta), rm)
+    assert np.array_equal(to_bits(vals), rv)
+
+
+def _y1_like(rng, T, F, shift=1.28):
+    return bf16_bits_from_f32(rng.standard_normal((T, F), dtype=np.float32) - np.float32(shift))
+
+
+@pytest.mark.parametrize("T,F", [(64, 64), (128, 512), (192, 1088), (512, 1024)])
+def test_sqrelu_vnm_compress(T, F):
+    rng = np.random.default_rng(T + F)
+    y1 = _y1_like(rng, T, F)
+    # corner cases: dead block, fully tied columns, a block with one live column, +-0, large values
+    y1[:64, 0:8] = 0xBF80
+    y1[:64, 8:16] = 0x3F80
+    y1[:64, 16:24] = 0x8000
+    y1[:64, 17] = 0x4000
+    y1[:64, 24:32] = 0x0000
+    y1[5, 24:32] = [0x3F80, 0x3F80, 0x4000, 0x4000, 0x3F80, 0x4000, 0x3F80, 0x4000]
+    y1[:64, 32:40] = 0x4580                      # 4096^2 = 2^24: ordered fp32 sums saturate
+    y1[1:64, 33] = 0x3F80
+    y1[0, 34] = 0x4581
+    vals, meta, colidx = sffn.sqrelu_vnm_compress(to_dev(y1))
+    rv, rm, rc = oracle.sqrelu_vnm_compress(y1)
+    assert np.array_equal(to_bits(colidx), rc)
+    assert np.array_equal(to_bits(meta), rm)
+    assert np.array_equal(to_bits(vals), rv)
+
+
+@pytest.mark.parametrize("T,F", [(64, 64), (192, 1088), (512, 4096)])
+def test_dsqrelu_vnm(T, F):
+    rng = np.random.default_rng(T * 5 + F)
+    y1 = _y1_like(rng, T, F, 0.8)
+    dy2 = rnd_bits(rng, (T, F))
+    rv, rm, rc = oracle.sqrelu_vnm_compress(y1)
+    dvals = sffn.dsqrelu_vnm(to_dev(dy2), to_dev(y1), to_dev(rm), to_dev(rc))
+    assert np.array_equal(to_bits(dvals), oracle.dsqrelu_vnm(dy2, y1, rm, rc))
+
+
+@pytest.mark.parametrize("T,N,K", [(64, 64, 64), (192, 320, 448), (512, 1024, 256), (384, 256, 2048)])
+def test_spmm24_fwd_and_dgrad(T, N, K):
+    rng = np.random.default_rng(T + 3 * N + 7 * K)
+    X = rnd_bits(rng, (T, K))
+    W = rnd_bits(rng, (N, K), 0.02)
+    bias = rng.standard_normal(N).astype(np.float32)
+    wv, wm = oracle.prune24_compress(W, oracle.sparse24.SOFT)
+    dX, dwv, dwm, dbias = to_dev(X), to_dev(wv), to_dev(wm), to_dev(bias)
+    assert_gemm_close(to_bits(sffn.spmm24_fwd(dX, dwv, dwm, dbias)), oracle.spmm24(X, wv, wm, bias), "fwd+bias")
+    assert_gemm_close(to_bits(sffn.spmm24_fwd(dX, dwv, dwm, None)), oracle.spmm24(X, wv, wm, None), "fwd")
+    assert_gemm_close(to_bits(sffn.spmm24_dgrad(dX, dwv, dwm)), oracle.spmm24(X, wv, wm, None), "dgrad")
+
+
+@pytest.mark.parametrize("T,F,D", [(64, 64, 64), (192, 448, 320), (512, 1024, 256), (256, 2048, 192)])
+def test_vnm_spmm_and_wgrad(T, F, D):
+    rng = np.random.default_rng(T + 3 * F + 7 * D)
+    y1 = _y1_like(rng, T, F, 0.8)
+    av, am, ac = oracle.sqrelu_vnm_compress(y1)
+    W2 = rnd_bits(rng, (D, F), 0.02)              # [N, Kfull]
+    W1 = rnd_bits(rng, (F, D), 0.02)              # [Kfull, N]
+    G = rnd_bits(rng, (T, D))
+    dav, dam, dac = to_dev(av), to_dev(am), to_dev(ac)
+    assert_gemm_close(to_bits(sffn.vnm_spmm(dav, dam, dac, to_dev(W2), 0)), oracle.vnm_spmm(av, am, ac, W2, 0), "y3")
+    assert_gemm_close(to_bits(sffn.vnm_spmm(dav, dam, dac, to_dev(W1), 1)), oracle.vnm_spmm(av, am, ac, W1, 1), "dX")
+    assert_gemm_close(to_bits(sffn.vnm_wgrad(dav, dam, dac, to_dev(G), 1)), oracle.vnm_wgrad(av, am, ac, G, 1), "dW1")
+    assert_gemm_close(to_bits(sffn.vnm_wgrad(dav, dam, dac, to_dev(G), 0)), oracle.vnm_wgrad(av, am, ac, G, 0), "dW2")
+
+
+def test_gemm_exact_on_small_integers():
+    """Products and sums of small integers are exact in fp32, so the GEMMs must match bit for bit: catches any
+    operand-layout or metadata slip that a tolerance could hide."""
+    rng = np.random.default_rng(77)
+    T, N, K = 128, 192, 256
+    X = bf16_bits_from_f32(rng.integers(-3, 4, (T, K)).astype(np.float32))
+    W = bf16_bits_from_f32(rng.integers(-3, 4, (N, K)).astype(np.float32))
+    wv, wm = oracle.prune24_compress(W)
+    got = to_bits(sffn.spmm24_fwd(to_dev(X), to_dev(wv), to_dev(wm), None))
+    assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.spmm24(X, wv, wm, None)))
+    y2 = bf16_bits_from_f32((rng.integers(0, 4, (T, K)) * (rng.random((T, K)) < 0.3)).astype(np.float32))
+    av, am, ac = oracle.vnm_compress(y2)
+    Wd = bf16_bits_from_f32(rng.integers(-3, 4, (N, K)).astype(np.float32))
+    G = bf16_bits_from_f32(rng.integers(-2, 3, (T, N)).astype(np.float32))
+    for kmaj, w in ((0, Wd), (1, np.ascontiguousarray(Wd.T))):
+        got = to_bits(sffn.vnm_spmm(to_dev(av), to_dev(am), to_dev(ac), to_dev(w), kmaj))
+        assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.vnm_spmm(av, am, ac, w, kmaj)))
+    for fmaj in (0, 1):
+        got = to_bits(sffn.vnm_wgrad(to_dev(av), to_dev(am), to_dev(ac), to_dev(G), fmaj))
+        assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.vnm_wgrad(av, am, ac, G, fmaj)))
+
+
+def _teacher_forced_step_check(T, D, F, mode, seed):
+    inp = make_ffn_inputs(T, D, F, seed=seed)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    (Y3, dX, dW1, dW2), step = sffn.ffn_sparse_step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"], mode)
+    torch.cuda.synchronize()
+    s = {k: to_bits(v) for k, v in step.saved().items()}
+    # each oracle stage consumes the GPU's output of the stage before it
+    rv, rm = oracle.prune24_compress(inp["W1"], mode)
+    assert np.array_equal(s["w1_vals"], rv) and np.array_equal(s["w1_meta"], rm)
+    assert_gemm_close(s["y1"], oracle.spmm24(inp["X"], s["w1_vals"], s["w1_meta"], inp["b1"]), "y1")
+    yv, ym, yc = oracle.sqrelu_vnm_compress(s["y1"])
+    assert np.array_equal(s["colidx"], yc) and np.array_equal(s["y2_meta"], ym) and np.array_equal(s["y2_vals"], yv)
+    assert_gemm_close(to_bits(Y3), oracle.vnm_spmm(yv, ym, yc, inp["W2"], 0), "y3")
+    rv2, rm2 = oracle.prune24_compress(np.ascontiguousarray(inp["W2"].T), mode)
+    assert np.array_equal(s["w2t_vals"], rv2) and np.array_equal(s["w2t_meta"], rm2)
+    assert_gemm_close(s["dy2"], oracle.spmm24(inp["dY"], rv2, rm2, None), "dy2")
+    dv = oracle.dsqrelu_vnm(s["dy2"], s["y1"], ym, yc)
+    assert np.array_equal(s["dy1_vals"], dv)
+    assert_gemm_close(to_bits(dW2), oracle.vnm_wgrad(yv, ym, yc, inp["dY"], 0), "dW2")
+    assert_gemm_close(to_bits(dX), oracle.vnm_spmm(dv, ym, yc, inp["W1"], 1), "dX")
+    assert_gemm_close(to_bits(dW1), oracle.vnm_wgrad(dv, ym, yc, inp["X"], 1), "dW1")
+    return inp, s, dict(Y3=to_bits(Y3), dX=to_bits(dX), dW1=to_bits(dW1), dW2=to_bits(dW2))
+
+
+@pytest.mark.parametrize("mode", [sffn.MODE_HARD, sffn.MODE_SOFT])
+def test_ffn_sparse_step_tiny_config(mode):
+    """configs[0]: d_model 256, d_ff 1024, 512 tokens, seed 0; teacher-forced stage by stage, plus the
+    free-running comparison against the oracle's own end-to-end run."""
+    inp, s, outs = _teacher_forced_step_check(512, 256, 1024, mode, seed=0)
+    ref = oracle.ffn_sparse_step_ref(mode=mode, **inp)
+    agree = np.mean(ref["colidx"] == s["colidx"])
+    assert agree > 0.99, agree
+    zero_frac = np.mean(oracle.sqrelu(s["y1"]) == 0)
+    if mode == sffn.MODE_HARD:          # the workload's bias is sized for the unshrunk 2:4 weights
+        assert abs(zero_frac - 0.9) < 0.01
+    for k in ("Y3", "dX", "dW1", "dW2"):
+        rk = "y3" if k == "Y3" else k
+        g, r = oracle.bits_to_f64(outs[k]), oracle.bits_to_f64(ref[rk])
+        assert np.linalg.norm(g - r) / np.linalg.norm(r) < 0.05, k      # reported, loose: masks may flip on near ties
+
+
+def test_ffn_sparse_step_ragged_shape():
+    _teacher_forced_step_check(192, 320, 448, sffn.MODE_SOFT, seed=3)
+
+
+def test_step_is_deterministic_and_reusable():
+    inp = make_ffn_inputs(256, 128, 512, seed=4)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    step = sffn.FfnStep(256, 128, 512)
+    a = [to_bits(t).copy() for t in step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    b = [to_bits(t).copy() for t in step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
