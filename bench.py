@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparsified FFN training step (one pass of Alg. 1 + Alg. 2 = one "step") on one MI355X.
+
+Prints one JSON line: dense-equivalent TFLOP/s of ffn_sparse_step (12*T*D*F flop per step), the
+speed-up over a dense bf16 FFN step built from hipBLASLt GEMMs (torch.matmul) timed in the same
+process, a roofline record for the kernel that takes most of the step, and the CPU oracle timed
+on the host cores as a reported baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_flops(stage, T, D, F):
+    """Multiply-adds the method itself needs (non-zero products), times two, per launch."""
+    tdf = float(T) * D * F
+    return {"step/y1": tdf, "step/dy2": tdf,                      # 2:4 weights: half of K survives
+            "step/y3": 0.5 * tdf, "step/dX": 0.5 * tdf,          # V:2:8 activations: a quarter survives
+            "step/dW2": 0.5 * tdf, "step/dW1": 0.5 * tdf}.get(stage)
+
+
+def executed_flops(stage, T, D, F):
+    """Flops the matrix cores are issued for (dense-equivalent of the instructions used)."""
+    tdf = float(T) * D * F
+    return {"step/y1": 2 * tdf, "step/dy2": 2 * tdf, "step/y3": 2 * tdf, "step/dX": 2 * tdf,
+            "step/dW2": 2 * tdf, "step/dW1": 2 * tdf}.get(stage)
+
+
+KERNEL_OF_STAGE = {"step/y1": "gemm_nt_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dy2": "gemm_nt_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
+                   "step/y3": "gemm_nt_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dX": "gemm_nt_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
+                   "step/dW2": "gemm_nt_kernel<dense A, mfma_f32_32x32x16_bf16>", "step/dW1": "gemm_nt_kernel<dense A, mfma_f32_32x32x16_bf16>"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="1b", help="tiny | 1b | 7b | 70b | moe_expert")
+    ap.add_argument("--zero-fraction", type=float, default=0.90)
+    ap.add_argument("--mode", default="hard", choices=["hard", "soft"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the step shards by tokens; no multi-GPU path is built). Use --gpus 1.")
+
+    import numpy as np
+    import torch
+    import paper_2602_06183_amd as sffn
+    from workload import CONFIGS, make_ffn_inputs
+
+    sffn.load()                     # fails loudly when the HIP library is missing
+    T, D, F = CONFIGS[args.workload]
+    mode = sffn.MODE_SOFT if args.mode == "soft" else sffn.MODE_HARD
+    inp = make_ffn_inputs(T, D, F, seed=0, zero_fraction=args.zero_fraction)
+
+    def dev(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+        return torch.from_numpy(a).cuda()
+
+    X, W1, W2, b1, dY = (dev(inp[k]) for k in ("X", "W1", "W2", "b1", "dY"))
+    step = sffn.FfnStep(T, D, F, mode)
+    flops = 12.0 * T * D * F
+
+    # ---- dense bf16 FFN step on hipBLASLt (torch.matmul), same shapes, same process -------------
+    try:
+        torch.backends.cuda.preferred_blas_library("hipblaslt")
+    except Exception:
+        pass
+    b1h = b1.to(torch.bfloat16)
+    y1 = torch.empty((T, F), dtype=torch.bfloat16, device="cuda")
+    y2, dy2, dy1 = torch.empty_like(y1), torch.empty_like(y1), torch.empty_like(y1)
+    y3, dXd = torch.empty((T, D), dtype=torch.bfloat16, device="cuda"), torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+    dW1d, dW2d = torch.empty_like(W1), torch.empty_like(W2)
+    W1t, W2t = W1.t(), W2.t()
+
+    def dense_step():
+        torch.addmm(b1h, X, W1t, out=y1)                 # eq. (1)
+        torch.clamp_min(y1, 0.0, out=y2); y2.mul_(y2)             # eq. (2)
+        torch.mm(y2, W2t, out=y3)                        # eq. (3)
+        torch.mm(dY, W2, out=dy2)                        # eq. (4)
+        torch.mm(dY.t(), y2, out=dW2d)                   # eq. (5)
+        torch.clamp_min(y1, 0.0, out=dy1); dy1.mul_(dy2).mul_(2.0) # eq. (6)
+        torch.mm(dy1, W1, out=dXd)                       # eq. (7)
+        torch.mm(dy1.t(), X, out=dW1d)                   # eq. (8)
+
+    def sparse_step():
+        step(X, W1, W2, b1, dY)
+
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    for _ in range(args.warmup):
+        sparse_step()
+        dense_step()
+    ms_sparse = timed(sparse_step, args.steps)          # the timed region: exactly --steps steps
+    ms_dense = timed(dense_step, args.steps)
+    ms_sparse2 = timed(sparse_step, args.steps)         # second, interleaved pass: clock drift check
+    ms_dense2 = timed(dense_step, args.steps)
+
+    # ---- per-launch durations from HIP events on the stream the kernels run on --------------------
+    sffn.profile_enable(True)
+    acc = {}
+    nprof = max(3, min(10, args.steps))
+    for _ in range(nprof):
+        sparse_step()
+        for name, ms in sffn.profile_read():
+            acc[name] = acc.get(name, 0.0) + ms / nprof
+    sffn.profile_enable(False)
+    by_kernel = {}
+    for name, ms in acc.items():
+        k = KERNEL_OF_STAGE.get(name, name)
+        by_kernel.setdefault(k, []).append((name, ms))
+    dom_kernel = max(by_kernel, key=lambda k: sum(ms for _, ms in by_kernel[k]))
+    launches = by_kernel[dom_kernel]
+    avg_ms = sum(ms for _, ms in launches) / len(launches)
+    alg = sum(algorithmic_flops(n, T, D, F) or 0.0 for n, _ in launches) / len(launches)
+    exe = sum(executed_flops(n, T, D, F) or 0.0 for n, _ in launches) / len(launches)
+    achieved = alg / (avg_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(dom_kernel)
+    roofline = {"bound": "mfma", "kernel": dom_kernel, "launches_per_step": len(launches), "avg_launch_ms": round(avg_ms, 4),
+                "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
+                "issued": round(exe / (avg_ms * 1e-3) / 1e12, 2), "issued_frac": round(exe / (avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+
+    # ---- CPU oracle on the host cores: a bounded token sample of the same workload ---------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        Ts = min(T, max(64, (int(3.0e11 / (12.0 * D * F)) // 64) * 64))      # about 0.3 TFLOP of fp64 matmul
+        t0 = time.perf_counter()
+        oracle.ffn_sparse_step_ref(inp["X"][:Ts], inp["W1"], inp["W2"], inp["b1"], inp["dY"][:Ts], mode)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(12.0 * Ts * D * F / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+               "sample": "oracle.ffn_sparse_step_ref on the first %d of %d tokens (same D, F, weights), %.1f s" % (Ts, T, dt)}
+
+    value = flops / (ms_sparse * 1e-3) / 1e12
+    out = {
+        "metric": "sparse FFN fwd+bwd TFLOP/s (dense-equiv) & speedup vs dense bf16, 1 MI355X",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_sparse, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: one FFN layer, T=%d tokens, d_model=%d, d_ff=%d, 2:4 weights (%s), V:N:M 64:2:8 SquaredReLU, zero fraction %.2f, seed 0"
+                   % (args.workload, T, D, F, args.mode, args.zero_fraction)},
+        "frac_of_mfma_peak": round(value / MFMA_BF16_PEAK_TFLOPS, 4),
+        "dense_ms_per_step": round(ms_dense, 4), "dense_tflops": round(flops / (ms_dense * 1e-3) / 1e12, 2),
+        "dense_frac_of_mfma_peak": round(flops / (ms_dense * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "speedup_vs_dense": round(ms_dense / ms_sparse, 4),
+        "second_pass": {"ms_per_step": round(ms_sparse2, 4), "dense_ms_per_step": round(ms_dense2, 4)},
+        "stage_ms": {k: round(v, 4) for k, v in acc.items()},
+        "roofline": roofline, "cpu_baseline": cpu,
+        "paper_context": "paper reports 1.4-1.5x for 2:4 GEMMs and 1.4-1.7x end-to-end on NVIDIA sparse tensor cores (Sections 1, 5.2.3); context, not a target",
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

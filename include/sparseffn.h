@@ -128,6 +128,13 @@ int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, 
                     const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
                     uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
 
+/* Measurement aid (not part of the method): when enabled, ffn_sparse_step records a HIP event on the
+ * caller's stream behind every kernel launch.  sffn_profile_read() waits for the last event of the
+ * most recent step and returns the number of launches, filling ms[i] (duration of launch i) and
+ * names[i] (static strings naming the stage).  Not thread-safe; enable/disable create/destroy events. */
+int sffn_profile_enable(int on);
+int sffn_profile_read(float* ms, const char** names, int max_n);
+
 #ifdef __cplusplus
 }
 #endif

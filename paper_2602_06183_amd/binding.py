@@ -59,6 +59,8 @@ def load():
     lib.dsqrelu_vnm.argtypes = [p, p, p, p, i64, i64, i32, i32, p, p]
     lib.vnm_wgrad.argtypes = [p, p, p, p, i64, i64, i64, i32, i32, i32, p, p, sz, p]
     lib.ffn_sparse_step.argtypes = [ctypes.POINTER(_Cfg)] + [p] * 9 + [p, sz, p]
+    lib.sffn_profile_enable.argtypes = [i32]
+    lib.sffn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_char_p), i32]
     _LIB = lib
     return lib
 
@@ -91,6 +93,20 @@ def _u8(shape, dev):
 
 def version():
     return load().sffn_version()
+
+
+def profile_enable(on=True):
+    _check(load().sffn_profile_enable(int(on)))
+
+
+def profile_read():
+    """[(stage name, milliseconds)] for every kernel launch of the most recent ffn_sparse_step."""
+    ms = (ctypes.c_float * 32)()
+    names = (ctypes.c_char_p * 32)()
+    n = load().sffn_profile_read(ms, names, 32)
+    if n < 0:
+        _check(n)
+    return [(names[i].decode(), float(ms[i])) for i in range(n)]
 
 
 def _cfg(T, D, F, mode=MODE_HARD, V=64, M=8):

@@ -27,6 +27,17 @@ inline bool fits_int(int64_t v) { return v < ((int64_t)1 << 31); }
 
 #define REQUIRE(cond, code, msg) do { if (!(cond)) return fail(code, "%s", msg); } while (0)
 #define LAUNCH(expr, where) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return hipfail(e_, where); } while (0)
+// inside ffn_sparse_step: launch, then (when profiling) drop an event behind it
+#define STAGE(expr, where) do { LAUNCH(expr, where); if (g_prof_on && g_prof_n < kMaxStages) { g_prof_name[g_prof_n] = where; \
+        ++g_prof_n; (void)hipEventRecord(g_prof_ev[g_prof_n], s); } } while (0)
+
+// Optional per-launch timing of ffn_sparse_step (measurement aid): events recorded on the caller's
+// stream between consecutive launches.
+constexpr int kMaxStages = 24;
+bool g_prof_on = false;
+hipEvent_t g_prof_ev[kMaxStages + 1];
+const char* g_prof_name[kMaxStages];
+int g_prof_n = 0;
 
 struct FullLayout {
     sffn_ws_layout pub;
@@ -223,26 +234,53 @@ int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, 
     uint16_t* a24v = (uint16_t*)(ws + L.a24_vals);      uint8_t* a24m = ws + L.a24_meta;
     uint16_t* at = (uint16_t*)(ws + L.at);
 
+    if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
     // ---- Alg. 1 -------------------------------------------------------------------------------
-    LAUNCH(launch_prune24(W1, F, D, D, 0, cfg->mode, w1v, w1m, s), "step/prune24(W1)");
-    LAUNCH(launch_gemm_nt(1, w1v, w1m, X, b1, F, T, D, 1, y1, F, s), "step/y1");                 // eq. (1)
-    LAUNCH(launch_sqrelu_vnm_compress(y1, T, F, y2v, y2m, cix, s), "step/sqrelu_vnm_compress");   // eq. (2) + V:N:M
-    LAUNCH(launch_vnm_to_24(y2v, y2m, cix, T, F, a24v, a24m, s), "step/y2->2:4");
-    LAUNCH(launch_gemm_nt(1, a24v, a24m, W2, nullptr, T, D, F, 0, Y3, D, s), "step/y3");          // eq. (3)
+    STAGE(launch_prune24(W1, F, D, D, 0, cfg->mode, w1v, w1m, s), "step/prune24(W1)");
+    STAGE(launch_gemm_nt(1, w1v, w1m, X, b1, F, T, D, 1, y1, F, s), "step/y1");                 // eq. (1)
+    STAGE(launch_sqrelu_vnm_compress(y1, T, F, y2v, y2m, cix, s), "step/sqrelu_vnm_compress");   // eq. (2) + V:N:M
+    STAGE(launch_vnm_to_24(y2v, y2m, cix, T, F, a24v, a24m, s), "step/y2->2:4");
+    STAGE(launch_gemm_nt(1, a24v, a24m, W2, nullptr, T, D, F, 0, Y3, D, s), "step/y3");          // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
-    LAUNCH(launch_prune24(W2, F, D, F, 1, cfg->mode, w2v, w2m, s), "step/prune24(W2.T)");
-    LAUNCH(launch_gemm_nt(1, w2v, w2m, dY, nullptr, F, T, D, 1, dy2, F, s), "step/dy2");          // eq. (4)
-    LAUNCH(launch_vnm_expand_t(y2v, y2m, cix, T, F, at, s), "step/y2 expand");
-    LAUNCH(launch_transpose(dY, T, D, D, dyt, s), "step/dY.T");
-    LAUNCH(launch_gemm_nt(0, at, nullptr, dyt, nullptr, F, D, T, 1, dW2, F, s), "step/dW2");      // eq. (5)
-    LAUNCH(launch_dsqrelu_vnm(dy2, y1, y2m, cix, T, F, dy1v, s), "step/dsqrelu_vnm");             // eq. (6)
-    LAUNCH(launch_vnm_to_24(dy1v, y2m, cix, T, F, a24v, a24m, s), "step/dy1->2:4");
-    LAUNCH(launch_transpose(W1, F, D, D, w1t, s), "step/W1.T");
-    LAUNCH(launch_gemm_nt(1, a24v, a24m, w1t, nullptr, T, D, F, 0, dX, D, s), "step/dX");         // eq. (7)
-    LAUNCH(launch_vnm_expand_t(dy1v, y2m, cix, T, F, at, s), "step/dy1 expand");
-    LAUNCH(launch_transpose(X, T, D, D, xt, s), "step/X.T");
-    LAUNCH(launch_gemm_nt(0, at, nullptr, xt, nullptr, F, D, T, 0, dW1, D, s), "step/dW1");       // eq. (8)
+    STAGE(launch_prune24(W2, F, D, F, 1, cfg->mode, w2v, w2m, s), "step/prune24(W2.T)");
+    STAGE(launch_gemm_nt(1, w2v, w2m, dY, nullptr, F, T, D, 1, dy2, F, s), "step/dy2");          // eq. (4)
+    STAGE(launch_vnm_expand_t(y2v, y2m, cix, T, F, at, s), "step/y2 expand");
+    STAGE(launch_transpose(dY, T, D, D, dyt, s), "step/dY.T");
+    STAGE(launch_gemm_nt(0, at, nullptr, dyt, nullptr, F, D, T, 1, dW2, F, s), "step/dW2");      // eq. (5)
+    STAGE(launch_dsqrelu_vnm(dy2, y1, y2m, cix, T, F, dy1v, s), "step/dsqrelu_vnm");             // eq. (6)
+    STAGE(launch_vnm_to_24(dy1v, y2m, cix, T, F, a24v, a24m, s), "step/dy1->2:4");
+    STAGE(launch_transpose(W1, F, D, D, w1t, s), "step/W1.T");
+    STAGE(launch_gemm_nt(1, a24v, a24m, w1t, nullptr, T, D, F, 0, dX, D, s), "step/dX");         // eq. (7)
+    STAGE(launch_vnm_expand_t(dy1v, y2m, cix, T, F, at, s), "step/dy1 expand");
+    STAGE(launch_transpose(X, T, D, D, xt, s), "step/X.T");
+    STAGE(launch_gemm_nt(0, at, nullptr, xt, nullptr, F, D, T, 0, dW1, D, s), "step/dW1");       // eq. (8)
     return SFFN_OK;
+}
+
+int sffn_profile_enable(int on) {
+    if (on && !g_prof_on) {
+        for (int i = 0; i <= kMaxStages; ++i)
+            if (hipEventCreate(&g_prof_ev[i]) != hipSuccess) return fail(SFFN_EHIP, "%s", "sffn_profile_enable: hipEventCreate failed");
+        g_prof_on = true;
+    } else if (!on && g_prof_on) {
+        for (int i = 0; i <= kMaxStages; ++i) (void)hipEventDestroy(g_prof_ev[i]);
+        g_prof_on = false;
+    }
+    g_prof_n = 0;
+    return SFFN_OK;
+}
+
+int sffn_profile_read(float* ms, const char** names, int max_n) {
+    if (!g_prof_on || g_prof_n == 0) return 0;
+    if (hipEventSynchronize(g_prof_ev[g_prof_n]) != hipSuccess) return fail(SFFN_EHIP, "%s", "sffn_profile_read: hipEventSynchronize failed");
+    const int n = g_prof_n < max_n ? g_prof_n : max_n;
+    for (int i = 0; i < n; ++i) {
+        float t = 0.f;
+        (void)hipEventElapsedTime(&t, g_prof_ev[i], g_prof_ev[i + 1]);
+        if (ms) ms[i] = t;
+        if (names) names[i] = g_prof_name[i];
+    }
+    return n;
 }
 
 }  // extern "C"
