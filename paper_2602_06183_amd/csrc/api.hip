@@ -257,6 +257,13 @@ int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, 
     return SFFN_OK;
 }
 
+int sffn_tune(int key, int value) {
+    if (key == 0) g_tile_sparse = value;
+    else if (key == 1) g_tile_dense = value;
+    else return fail(SFFN_EINVAL, "%s", "sffn_tune: unknown key");
+    return SFFN_OK;
+}
+
 int sffn_profile_enable(int on) {
     if (on && !g_prof_on) {
         for (int i = 0; i <= kMaxStages; ++i)

@@ -247,10 +247,21 @@ static hipError_t launch_one(const uint16_t* a_vals, const uint8_t* a_meta, cons
     return hipGetLastError();
 }
 
+int g_tile_sparse = 0, g_tile_dense = 0;   // 0: 128x128, 1: 256x128, 2: 128x256, 3: 256x256 (BM x BN), 4: pipelined 256x256
+
+hipError_t launch_gemm_nt_v2(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
+                             int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
+
 hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
                           int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
-    if (sparse_a) return launch_one<true, 128, 128>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, s);
-    return launch_one<false, 128, 128>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, s);
+    if ((sparse_a ? g_tile_sparse : g_tile_dense) == 4)
+        return launch_gemm_nt_v2(sparse_a, a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, s);
+#define GO(SP, BM, BN) return launch_one<SP, BM, BN>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, s)
+    if (sparse_a) {
+        switch (g_tile_sparse) { case 1: GO(true, 256, 128); case 2: GO(true, 128, 256); case 3: GO(true, 256, 256); default: GO(true, 128, 128); }
+    }
+    switch (g_tile_dense) { case 1: GO(false, 256, 128); case 2: GO(false, 128, 256); case 3: GO(false, 256, 256); default: GO(false, 128, 128); }
+#undef GO
 }
 
 }  // namespace sffn

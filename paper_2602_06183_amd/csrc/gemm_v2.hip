@@ -1,0 +1,265 @@
+// Pipelined tile kernel for the six contractions: C[i, j] = sum_k A[i, k] * B[j, k] with a 256 x 256
+// workgroup tile, 8 wavefronts (2 along i x 4 along j, 128 x 64 each, two wavefronts per SIMD so one
+// hides the other's LDS latency), operand tiles streamed HBM -> LDS with global_load_lds_dwordx4 into
+// a ring of LDS stages (no register staging), XOR-swizzled 16-byte chunks so that the b128 fragment
+// reads are bank-conflict free without padding.
+//   SPARSE: A packed 2:4 -> v_smfmac_f32_32x32x32_bf16; ring of 3 stages of 64 k (50 KB each).
+//   dense : v_mfma_f32_32x32x16_bf16; ring of 4 stages of 32 k (32 KB each).
+// Register layouts of the two instructions are documented in gemm.hip.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace sffn {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+namespace {
+
+union Frag8 { uint4 u; bf16x8 v; };
+union Frag16 { uint4 u[2]; bf16x16 v; };
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void glb_void;
+
+// The LDS-DMA loads are issued through inline assembly so that their completion is tracked only by the
+// explicit vmcnt waits of the main loop (the ring keeps the loads of the next tiles in flight across
+// the fragment reads of the current one).  m0 carries the wave-uniform LDS destination.
+__device__ __forceinline__ void dma16(const void* g, unsigned char* lds_wave_base) {
+    // every lane fetches 16 bytes; the wave's 64 chunks land at lds_wave_base + 16 * lane
+    const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void*)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(dst) : "m0", "memory");
+}
+__device__ __forceinline__ void dma4(const void* g, unsigned char* lds_wave_base) {
+    const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void*)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(dst) : "m0", "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    // gfx9 s_waitcnt immediate: vmcnt = bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8 (left at "no wait")
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+template <bool SPARSE>
+struct Cfg {
+    static constexpr int BM = 256, BN = 256;
+    static constexpr int BK = SPARSE ? 64 : 32;
+    static constexpr int NSTAGE = SPARSE ? 3 : 4;
+    static constexpr int A_ROW = 64;                        // bytes per A row per stage (32 survivors or 32 dense k)
+    static constexpr int B_ROW = SPARSE ? 128 : 64;
+    static constexpr int A_BYTES = BM * A_ROW, B_BYTES = BN * B_ROW, META_BYTES = SPARSE ? BM * 8 : 0;
+    static constexpr int STAGE = A_BYTES + B_BYTES + META_BYTES;
+    static constexpr int LOADS = (A_BYTES + B_BYTES) / 1024 / 8 + (SPARSE ? 1 : 0);   // per wave per stage
+};
+
+}  // namespace
+
+template <bool SPARSE, bool OUT_I_CONTIG>
+__global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restrict__ a_vals, const uint8_t* __restrict__ a_meta,
+                                                        const uint16_t* __restrict__ B, const float* __restrict__ bias,
+                                                        int Ra, int Rb, int K, uint16_t* __restrict__ out, int64_t ldo,
+                                                        int tiles_m, int tiles_n) {
+    using C = Cfg<SPARSE>;
+    constexpr int BM = C::BM, BN = C::BN, WM = 128, WN = 64, FM = 4, FN = 2;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[C::NSTAGE * C::STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    int tm, tn;
+    {
+        const int n = gridDim.x, pid = blockIdx.x, per = n >> 3;
+        const int L = (pid < per * 8) ? (pid & 7) * per + (pid >> 3) : pid;
+        constexpr int GROUP = 4;
+        const int width = GROUP * tiles_n, group = L / width, first = group * GROUP;
+        const int gsz = (tiles_m - first) < GROUP ? (tiles_m - first) : GROUP;
+        tm = first + (L % width) % gsz;
+        tn = (L % width) / gsz;
+    }
+    const int i0 = tm * BM, j0 = tn * BN;
+    const int lda = SPARSE ? K / 2 : K;
+
+    // ---- per-lane source addresses of the DMA loads (tile row clamped into the matrix: rows past the
+    //      edge only feed outputs that are never stored) ---------------------------------------------
+    constexpr int A_LD = C::A_BYTES / 1024 / 8;          // dma16 issues per wave for A
+    constexpr int B_LD = C::B_BYTES / 1024 / 8;
+    const uint16_t* a_src[A_LD];
+    const uint16_t* b_src[B_LD];
+    const uint8_t* m_src = nullptr;
+#pragma unroll
+    for (int n = 0; n < A_LD; ++n) {
+        const int row = (wave * A_LD + n) * 16 + (lane >> 2);             // 16 rows of 64 B per KB
+        const int c = (lane & 3) ^ ((row >> 2) & 3);
+        int gr = i0 + row; gr = gr < Ra ? gr : Ra - 1;
+        a_src[n] = a_vals + (int64_t)gr * lda + c * 8;
+    }
+#pragma unroll
+    for (int n = 0; n < B_LD; ++n) {
+        int row, c;
+        if (SPARSE) { row = (wave * B_LD + n) * 8 + (lane >> 3); c = (lane & 7) ^ ((row >> 1) & 7); }
+        else        { row = (wave * B_LD + n) * 16 + (lane >> 2); c = (lane & 3) ^ ((row >> 2) & 3); }
+        int gr = j0 + row; gr = gr < Rb ? gr : Rb - 1;
+        b_src[n] = B + (int64_t)gr * K + c * 8;
+    }
+    if (SPARSE) {
+        const int row = (wave * 64 + lane) >> 1;
+        int gr = i0 + row; gr = gr < Ra ? gr : Ra - 1;
+        m_src = a_meta + (int64_t)gr * (K / 8) + (lane & 1) * 4;
+    }
+    auto issue = [&](int kt, int stage) {
+        unsigned char* sa = smem + stage * C::STAGE;
+        unsigned char* sb = sa + C::A_BYTES;
+        unsigned char* sm = sb + C::B_BYTES;
+#pragma unroll
+        for (int n = 0; n < A_LD; ++n) dma16(a_src[n] + kt * 32, sa + (wave * A_LD + n) * 1024);
+#pragma unroll
+        for (int n = 0; n < B_LD; ++n) dma16(b_src[n] + kt * C::BK, sb + (wave * B_LD + n) * 1024);
+        if (SPARSE) dma4(m_src + kt * 8, sm + wave * 256);
+    };
+
+    // ---- per-lane LDS offsets of the fragment reads (inside a stage) --------------------------------
+    int a_off[FM], b_off[FN], m_off[FM];
+#pragma unroll
+    for (int a = 0; a < FM; ++a) {
+        const int row = wm * WM + a * 32 + l32;
+        a_off[a] = row * 64 + ((lh ^ ((row >> 2) & 3)) << 4);
+        m_off[a] = C::A_BYTES + C::B_BYTES + row * 8 + 2 * lh;
+    }
+#pragma unroll
+    for (int b = 0; b < FN; ++b) {
+        const int row = wn * WN + b * 32 + l32;
+        if (SPARSE) b_off[b] = C::A_BYTES + row * 128 + ((lh ^ ((row >> 1) & 7)) << 4);
+        else        b_off[b] = C::A_BYTES + row * 64 + ((lh ^ ((row >> 2) & 3)) << 4);
+    }
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int b = 0; b < FN; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
+
+    auto compute = [&](int stage) {
+        const unsigned char* st = smem + stage * C::STAGE;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            if (SPARSE) {
+                Frag8 fa[FM];
+                int idx[FM];
+                Frag16 fb[FN];
+#pragma unroll
+                for (int a = 0; a < FM; ++a) {
+                    fa[a].u = *reinterpret_cast<const uint4*>(st + (a_off[a] ^ (32 * ks)));
+                    idx[a] = *reinterpret_cast<const uint16_t*>(st + m_off[a] + 4 * ks);
+                }
+#pragma unroll
+                for (int b = 0; b < FN; ++b) {
+                    fb[b].u[0] = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ (64 * ks)));
+                    fb[b].u[1] = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ (64 * ks + 32)));
+                }
+#pragma unroll
+                for (int a = 0; a < FM; ++a)
+#pragma unroll
+                    for (int b = 0; b < FN; ++b)
+                        acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(fa[a].v, fb[b].v, acc[a][b], idx[a], 0, 0);
+            } else {
+                Frag8 fa[FM], fb[FN];
+#pragma unroll
+                for (int a = 0; a < FM; ++a) fa[a].u = *reinterpret_cast<const uint4*>(st + (a_off[a] ^ (32 * ks)));
+#pragma unroll
+                for (int b = 0; b < FN; ++b) fb[b].u = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ (32 * ks)));
+#pragma unroll
+                for (int a = 0; a < FM; ++a)
+#pragma unroll
+                    for (int b = 0; b < FN; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a].v, fb[b].v, acc[a][b], 0, 0, 0);
+            }
+        }
+    };
+
+    const int nk = K / C::BK;
+    constexpr int DIST = C::NSTAGE - 1;
+#pragma unroll
+    for (int p = 0; p < DIST; ++p) issue(p < nk ? p : nk - 1, p);
+    wait_vmcnt<(DIST - 1) * C::LOADS>();
+    __syncthreads();
+    int stage = 0, fill = DIST;
+    for (int kt = 0; kt < nk; ++kt) {
+        const int nxt = kt + DIST;
+        issue(nxt < nk ? nxt : nk - 1, fill);           // the stage being refilled held tile kt-1
+        compute(stage);
+        wait_vmcnt<(DIST - 1) * C::LOADS>();             // tile kt+1 has landed (this wave's part)
+        __syncthreads();
+        stage = (stage + 1 == C::NSTAGE) ? 0 : stage + 1;
+        fill = (fill + 1 == C::NSTAGE) ? 0 : fill + 1;
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    if (OUT_I_CONTIG) {
+#pragma unroll
+        for (int a = 0; a < FM; ++a)
+#pragma unroll
+            for (int b = 0; b < FN; ++b) {
+                const int j = j0 + wn * WN + b * 32 + l32;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int i = i0 + wm * WM + a * 32 + 8 * g + 4 * lh;
+                    if (j < Rb && i < Ra) {
+                        float v0 = acc[a][b][4 * g], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2], v3 = acc[a][b][4 * g + 3];
+                        if (bias) { const float4 bb = *reinterpret_cast<const float4*>(bias + i); v0 += bb.x; v1 += bb.y; v2 += bb.z; v3 += bb.w; }
+                        *reinterpret_cast<uint2*>(out + (int64_t)j * ldo + i) = make_uint2(f2bf(v0) | (f2bf(v1) << 16), f2bf(v2) | (f2bf(v3) << 16));
+                    }
+                }
+            }
+    } else {
+        constexpr int EP = WN * 2 + 16;
+        unsigned char* scratch = smem + wave * (32 * EP);
+#pragma unroll
+        for (int a = 0; a < FM; ++a) {
+#pragma unroll
+            for (int b = 0; b < FN; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 8 * (r >> 2) + 4 * lh + (r & 3);
+                    *reinterpret_cast<uint16_t*>(scratch + row * EP + (b * 32 + l32) * 2) = (uint16_t)f2bf(acc[a][b][r]);
+                }
+            __syncthreads();
+            constexpr int CH = WN / 8;
+#pragma unroll
+            for (int p = 0; p < 32 * CH / 64; ++p) {
+                const int e = lane + 64 * p, row = e / CH, ch = e % CH;
+                const int i = i0 + wm * WM + a * 32 + row, j = j0 + wn * WN + ch * 8;
+                if (i < Ra && j < Rb)
+                    *reinterpret_cast<uint4*>(out + (int64_t)i * ldo + j) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
+            }
+            __syncthreads();
+        }
+    }
+}
+
+template <bool SPARSE>
+static hipError_t launch_v2(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t Ra,
+                            int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
+    const int tiles_m = (int)((Ra + 255) / 256), tiles_n = (int)((Rb + 255) / 256);
+    dim3 grid((unsigned)(tiles_m * tiles_n));
+    if (out_i_contig)
+        hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
+                           out, ldo, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, false>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
+                           out, ldo, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_nt_v2(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
+                             int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
+    if (sparse_a) return launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, s);
+    return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, s);
+}
+
+}  // namespace sffn
