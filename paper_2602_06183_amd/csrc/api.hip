@@ -260,6 +260,7 @@ int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, 
 int sffn_tune(int key, int value) {
     if (key == 0) g_tile_sparse = value;
     else if (key == 1) g_tile_dense = value;
+    else if (key == 2) g_dbg = value;
     else return fail(SFFN_EINVAL, "%s", "sffn_tune: unknown key");
     return SFFN_OK;
 }

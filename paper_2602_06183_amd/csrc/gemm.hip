@@ -247,7 +247,7 @@ static hipError_t launch_one(const uint16_t* a_vals, const uint8_t* a_meta, cons
     return hipGetLastError();
 }
 
-int g_tile_sparse = 0, g_tile_dense = 0;   // 0: 128x128, 1: 256x128, 2: 128x256, 3: 256x256 (BM x BN), 4: pipelined 256x256
+int g_tile_sparse = 4, g_tile_dense = 4;   // 0: 128x128, 1: 256x128, 2: 128x256, 3: 256x256 (BM x BN), 4: pipelined 256x256
 
 hipError_t launch_gemm_nt_v2(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
                              int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);

@@ -60,7 +60,7 @@ template <bool SPARSE, bool OUT_I_CONTIG>
 __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restrict__ a_vals, const uint8_t* __restrict__ a_meta,
                                                         const uint16_t* __restrict__ B, const float* __restrict__ bias,
                                                         int Ra, int Rb, int K, uint16_t* __restrict__ out, int64_t ldo,
-                                                        int tiles_m, int tiles_n) {
+                                                        int tiles_m, int tiles_n, int dbg) {
     using C = Cfg<SPARSE>;
     constexpr int BM = C::BM, BN = C::BN, WM = 128, WN = 64, FM = 4, FN = 2;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[C::NSTAGE * C::STAGE];
@@ -99,8 +99,16 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
 #pragma unroll
     for (int n = 0; n < B_LD; ++n) {
         int row, c;
-        if (SPARSE) { row = (wave * B_LD + n) * 8 + (lane >> 3); c = (lane & 7) ^ ((row >> 1) & 7); }
-        else        { row = (wave * B_LD + n) * 16 + (lane >> 2); c = (lane & 3) ^ ((row >> 2) & 3); }
+        if (SPARSE) {
+            // the 128-byte k range of a row is kept as two 64-byte half rows (half-tile h at h * 16 KB), each
+            // laid out like the A tile, which keeps every 16-lane b128 read group on 64 distinct banks
+            const int blk = wave * B_LD + n, h = blk >> 4;
+            row = (blk & 15) * 16 + (lane >> 2);
+            c = h * 4 + ((lane & 3) ^ ((row >> 2) & 3));
+        } else {
+            row = (wave * B_LD + n) * 16 + (lane >> 2);
+            c = (lane & 3) ^ ((row >> 2) & 3);
+        }
         int gr = j0 + row; gr = gr < Rb ? gr : Rb - 1;
         b_src[n] = B + (int64_t)gr * K + c * 8;
     }
@@ -113,6 +121,17 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         unsigned char* sa = smem + stage * C::STAGE;
         unsigned char* sb = sa + C::A_BYTES;
         unsigned char* sm = sb + C::B_BYTES;
+        if (dbg & 4) {   // timing experiment only: pretend both operands are stored tile-major (contiguous chunks)
+            const int nkk = K / C::BK;
+            const unsigned char* ab = (const unsigned char*)a_vals + ((size_t)tm * nkk + kt) * C::A_BYTES;
+            const unsigned char* bb = (const unsigned char*)B + ((size_t)tn * nkk + kt) * C::B_BYTES;
+#pragma unroll
+            for (int n = 0; n < A_LD; ++n) dma16(ab + (wave * A_LD + n) * 1024 + lane * 16, sa + (wave * A_LD + n) * 1024);
+#pragma unroll
+            for (int n = 0; n < B_LD; ++n) dma16(bb + (wave * B_LD + n) * 1024 + lane * 16, sb + (wave * B_LD + n) * 1024);
+            if (SPARSE) dma4(a_meta + ((size_t)tm * nkk + kt) * C::META_BYTES + wave * 256 + lane * 4, sm + wave * 256);
+            return;
+        }
 #pragma unroll
         for (int n = 0; n < A_LD; ++n) dma16(a_src[n] + kt * 32, sa + (wave * A_LD + n) * 1024);
 #pragma unroll
@@ -131,8 +150,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
 #pragma unroll
     for (int b = 0; b < FN; ++b) {
         const int row = wn * WN + b * 32 + l32;
-        if (SPARSE) b_off[b] = C::A_BYTES + row * 128 + ((lh ^ ((row >> 1) & 7)) << 4);
-        else        b_off[b] = C::A_BYTES + row * 64 + ((lh ^ ((row >> 2) & 3)) << 4);
+        b_off[b] = C::A_BYTES + row * 64 + ((lh ^ ((row >> 2) & 3)) << 4);      // SPARSE: + 16 KB for the second k half
     }
 
     f32x16 acc[FM][FN];
@@ -143,42 +161,39 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
 
-    auto compute = [&](int stage) {
+    // Fragment sets: P feeds the first half of a stage's k range, Q the second.  Reads of one set are
+    // issued while the matrix cores work on the other, so LDS latency stays behind MFMA time.
+    struct FragSet {
+        Frag8 a[FM];
+        int idx[FM];
+        Frag16 b16[FN];     // SPARSE: 16 k-values per lane
+        Frag8 b8[FN];       // dense: 8 k-values per lane
+    };
+    auto read_frags = [&](FragSet& f, int stage, int ks) {
         const unsigned char* st = smem + stage * C::STAGE;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int a = 0; a < FM; ++a) {
+            f.a[a].u = *reinterpret_cast<const uint4*>(st + (a_off[a] ^ (32 * ks)));
+            if (SPARSE) f.idx[a] = *reinterpret_cast<const uint16_t*>(st + m_off[a] + 4 * ks);
+        }
+#pragma unroll
+        for (int b = 0; b < FN; ++b) {
             if (SPARSE) {
-                Frag8 fa[FM];
-                int idx[FM];
-                Frag16 fb[FN];
-#pragma unroll
-                for (int a = 0; a < FM; ++a) {
-                    fa[a].u = *reinterpret_cast<const uint4*>(st + (a_off[a] ^ (32 * ks)));
-                    idx[a] = *reinterpret_cast<const uint16_t*>(st + m_off[a] + 4 * ks);
-                }
-#pragma unroll
-                for (int b = 0; b < FN; ++b) {
-                    fb[b].u[0] = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ (64 * ks)));
-                    fb[b].u[1] = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ (64 * ks + 32)));
-                }
-#pragma unroll
-                for (int a = 0; a < FM; ++a)
-#pragma unroll
-                    for (int b = 0; b < FN; ++b)
-                        acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(fa[a].v, fb[b].v, acc[a][b], idx[a], 0, 0);
+                f.b16[b].u[0] = *reinterpret_cast<const uint4*>(st + b_off[b] + 16384 * ks);
+                f.b16[b].u[1] = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ 32) + 16384 * ks);
             } else {
-                Frag8 fa[FM], fb[FN];
-#pragma unroll
-                for (int a = 0; a < FM; ++a) fa[a].u = *reinterpret_cast<const uint4*>(st + (a_off[a] ^ (32 * ks)));
-#pragma unroll
-                for (int b = 0; b < FN; ++b) fb[b].u = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ (32 * ks)));
-#pragma unroll
-                for (int a = 0; a < FM; ++a)
-#pragma unroll
-                    for (int b = 0; b < FN; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a].v, fb[b].v, acc[a][b], 0, 0, 0);
+                f.b8[b].u = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ (32 * ks)));
             }
         }
+    };
+    auto mma = [&](const FragSet& f) {
+#pragma unroll
+        for (int a = 0; a < FM; ++a)
+#pragma unroll
+            for (int b = 0; b < FN; ++b) {
+                if (SPARSE) acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[a].v, f.b16[b].v, acc[a][b], f.idx[a], 0, 0);
+                else        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a].v, f.b8[b].v, acc[a][b], 0, 0, 0);
+            }
     };
 
     const int nk = K / C::BK;
@@ -187,14 +202,27 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     for (int p = 0; p < DIST; ++p) issue(p < nk ? p : nk - 1, p);
     wait_vmcnt<(DIST - 1) * C::LOADS>();
     __syncthreads();
+    FragSet P, Q;
+    read_frags(P, 0, 0);
     int stage = 0, fill = DIST;
     for (int kt = 0; kt < nk; ++kt) {
         const int nxt = kt + DIST;
-        issue(nxt < nk ? nxt : nk - 1, fill);           // the stage being refilled held tile kt-1
-        compute(stage);
-        wait_vmcnt<(DIST - 1) * C::LOADS>();             // tile kt+1 has landed (this wave's part)
-        __syncthreads();
-        stage = (stage + 1 == C::NSTAGE) ? 0 : stage + 1;
+        const int next_stage = (stage + 1 == C::NSTAGE) ? 0 : stage + 1;
+        if (!(dbg & 1)) issue(nxt < nk ? nxt : nk - 1, fill);            // the stage being refilled held tile kt-1
+        read_frags(Q, stage, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!(dbg & 2)) mma(P);
+        __builtin_amdgcn_sched_barrier(0);
+        // Q has arrived, tile kt+1 has landed (this wave's part); after the barrier every wave is done
+        // reading this stage and every wave's part of tile kt+1 is in LDS
+        __builtin_amdgcn_s_waitcnt(((DIST - 1) * C::LOADS & 0xF) | ((((DIST - 1) * C::LOADS) >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(P, next_stage, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!(dbg & 2)) mma(Q);
+        __builtin_amdgcn_sched_barrier(0);
+        stage = next_stage;
         fill = (fill + 1 == C::NSTAGE) ? 0 : fill + 1;
     }
     wait_vmcnt<0>();
@@ -242,6 +270,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     }
 }
 
+int g_dbg = 0;
+
 template <bool SPARSE>
 static hipError_t launch_v2(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t Ra,
                             int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
@@ -249,10 +279,10 @@ static hipError_t launch_v2(const uint16_t* a_vals, const uint8_t* a_meta, const
     dim3 grid((unsigned)(tiles_m * tiles_n));
     if (out_i_contig)
         hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
-                           out, ldo, tiles_m, tiles_n);
+                           out, ldo, tiles_m, tiles_n, g_dbg);
     else
         hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, false>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
-                           out, ldo, tiles_m, tiles_n);
+                           out, ldo, tiles_m, tiles_n, g_dbg);
     return hipGetLastError();
 }
 

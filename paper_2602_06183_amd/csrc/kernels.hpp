@@ -24,6 +24,6 @@ hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld
 hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
                           int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
 
-extern int g_tile_sparse, g_tile_dense;
+extern int g_tile_sparse, g_tile_dense, g_dbg;
 
 }  // namespace sffn
