@@ -34,9 +34,9 @@ def executed_flops(stage, T, D, F):
             "step/dW2": 2 * tdf, "step/dW1": 2 * tdf}.get(stage)
 
 
-KERNEL_OF_STAGE = {"step/y1": "gemm_nt_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dy2": "gemm_nt_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
-                   "step/y3": "gemm_nt_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dX": "gemm_nt_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
-                   "step/dW2": "gemm_nt_kernel<dense A, mfma_f32_32x32x16_bf16>", "step/dW1": "gemm_nt_kernel<dense A, mfma_f32_32x32x16_bf16>"}
+KERNEL_OF_STAGE = {"step/y1": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dy2": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
+                   "step/y3": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dX": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
+                   "step/dW2": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>", "step/dW1": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>"}
 
 
 def main():

@@ -41,7 +41,8 @@ int g_prof_n = 0;
 
 struct FullLayout {
     sffn_ws_layout pub;
-    size_t w1t, xt, dyt, a24_vals, a24_meta, at, total;
+    // internal operands of the GEMMs, all in the blocked layout
+    size_t w1_vblk, w1_mblk, w2t_vblk, w2t_mblk, x_blk, xt_blk, dy_blk, dyt_blk, w2_blk, w1t_blk, a24_vblk, a24_mblk, at_blk, total;
 };
 
 bool make_layout(const sffn_cfg* c, FullLayout* L) {
@@ -55,11 +56,13 @@ bool make_layout(const sffn_cfg* c, FullLayout* L) {
     L->pub.y2_vals = take(T * F / 2);      L->pub.y2_meta = take(T * F / 16);   L->pub.colidx = take(T / 64 * (F / 8) * 4);
     L->pub.dy2 = take(T * F * 2);
     L->pub.dy1_vals = take(T * F / 2);
-    L->w1t = take(D * F * 2);
-    L->xt = take(D * T * 2);
-    L->dyt = take(D * T * 2);
-    L->a24_vals = take(T * F);             L->a24_meta = take(T * F / 8);
-    L->at = take(F * T * 2);
+    L->w1_vblk = take(F * D);              L->w1_mblk = take(F * D / 8);
+    L->w2t_vblk = take(F * D);             L->w2t_mblk = take(F * D / 8);
+    L->x_blk = take(T * D * 2);            L->xt_blk = take(D * T * 2);
+    L->dy_blk = take(T * D * 2);           L->dyt_blk = take(D * T * 2);
+    L->w2_blk = take(D * F * 2);           L->w1t_blk = take(D * F * 2);
+    L->a24_vblk = take(T * F);             L->a24_mblk = take(T * F / 8);
+    L->at_blk = take(F * T * 2);
     L->total = off;
     L->pub.total = off;
     return true;
@@ -116,7 +119,7 @@ int sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, int V, int M, 
     REQUIRE(aligned16(y1) && aligned16(vals) && aligned16(meta) && aligned16(colidx), SFFN_EINVAL,
             "sqrelu_vnm_compress: pointers must be 16-byte aligned");
     REQUIRE(fits_int(T) && fits_int(F) && T / 64 < 65536, SFFN_EUNSUPPORTED, "sqrelu_vnm_compress: T too large");
-    LAUNCH(launch_sqrelu_vnm_compress(y1, T, F, vals, meta, colidx, (hipStream_t)stream), "sqrelu_vnm_compress");
+    LAUNCH(launch_sqrelu_vnm_compress(y1, T, F, vals, meta, colidx, nullptr, nullptr, (hipStream_t)stream), "sqrelu_vnm_compress");
     return SFFN_OK;
 }
 
@@ -163,7 +166,7 @@ int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_col
     LAUNCH(launch_vnm_to_24(a_vals, a_meta, a_colidx, T, Kfull, v24, m24, s), "vnm_spmm/to24");
     if (w_kmajor) {
         uint16_t* wt = (uint16_t*)(m24 + up256((size_t)T * Kfull / 8));
-        LAUNCH(launch_transpose(Wd, Kfull, N, ldw, wt, s), "vnm_spmm/transpose");
+        LAUNCH(launch_transpose(Wd, Kfull, N, ldw, wt, 0, nullptr, s), "vnm_spmm/transpose");
         W = wt;
     }
     LAUNCH(launch_gemm_nt(1, v24, m24, W, nullptr, T, N, Kfull, 0, out, N, s), "vnm_spmm/gemm");
@@ -178,7 +181,7 @@ int dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, co
     REQUIRE(aligned16(dy2) && aligned16(y1) && aligned16(meta) && aligned16(colidx) && aligned16(dvals), SFFN_EINVAL,
             "dsqrelu_vnm: pointers must be 16-byte aligned");
     REQUIRE(fits_int(T) && fits_int(F) && T < 65536, SFFN_EUNSUPPORTED, "dsqrelu_vnm: T must be below 65536");
-    LAUNCH(launch_dsqrelu_vnm(dy2, y1, meta, colidx, T, F, dvals, (hipStream_t)stream), "dsqrelu_vnm");
+    LAUNCH(launch_dsqrelu_vnm(dy2, y1, meta, colidx, T, F, dvals, nullptr, nullptr, (hipStream_t)stream), "dsqrelu_vnm");
     return SFFN_OK;
 }
 
@@ -197,8 +200,8 @@ int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_co
     hipStream_t s = (hipStream_t)stream;
     uint16_t* at = (uint16_t*)workspace;
     uint16_t* gt = (uint16_t*)((unsigned char*)workspace + up256((size_t)F * T * 2));
-    LAUNCH(launch_vnm_expand_t(a_vals, a_meta, a_colidx, T, F, at, s), "vnm_wgrad/expand");
-    LAUNCH(launch_transpose(G, T, N, N, gt, s), "vnm_wgrad/transpose");
+    LAUNCH(launch_vnm_expand_t(a_vals, a_meta, a_colidx, T, F, at, 0, s), "vnm_wgrad/expand");
+    LAUNCH(launch_transpose(G, T, N, N, gt, 0, nullptr, s), "vnm_wgrad/transpose");
     // C[i=f][j=n]; out_f_major: out[f*N + n] (j contiguous) else out[n*F + f] (i contiguous)
     if (out_f_major) LAUNCH(launch_gemm_nt(0, at, nullptr, gt, nullptr, F, N, T, 0, out, N, s), "vnm_wgrad/gemm");
     else             LAUNCH(launch_gemm_nt(0, at, nullptr, gt, nullptr, F, N, T, 1, out, F, s), "vnm_wgrad/gemm");
@@ -228,39 +231,41 @@ int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, 
     uint16_t* y2v = (uint16_t*)(ws + L.pub.y2_vals);    uint8_t* y2m = ws + L.pub.y2_meta;   uint8_t* cix = ws + L.pub.colidx;
     uint16_t* dy2 = (uint16_t*)(ws + L.pub.dy2);
     uint16_t* dy1v = (uint16_t*)(ws + L.pub.dy1_vals);
-    uint16_t* w1t = (uint16_t*)(ws + L.w1t);
-    uint16_t* xt = (uint16_t*)(ws + L.xt);
-    uint16_t* dyt = (uint16_t*)(ws + L.dyt);
-    uint16_t* a24v = (uint16_t*)(ws + L.a24_vals);      uint8_t* a24m = ws + L.a24_meta;
-    uint16_t* at = (uint16_t*)(ws + L.at);
+    uint16_t* w1vb = (uint16_t*)(ws + L.w1_vblk);       uint8_t* w1mb = ws + L.w1_mblk;
+    uint16_t* w2vb = (uint16_t*)(ws + L.w2t_vblk);      uint8_t* w2mb = ws + L.w2t_mblk;
+    uint16_t* xb = (uint16_t*)(ws + L.x_blk);           uint16_t* xtb = (uint16_t*)(ws + L.xt_blk);
+    uint16_t* dyb = (uint16_t*)(ws + L.dy_blk);         uint16_t* dytb = (uint16_t*)(ws + L.dyt_blk);
+    uint16_t* w2b = (uint16_t*)(ws + L.w2_blk);         uint16_t* w1tb = (uint16_t*)(ws + L.w1t_blk);
+    uint16_t* a24v = (uint16_t*)(ws + L.a24_vblk);      uint8_t* a24m = ws + L.a24_mblk;
+    uint16_t* atb = (uint16_t*)(ws + L.at_blk);
 
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
+    // Every GEMM operand is first brought into the blocked layout by the kernel that reads or produces it
+    // anyway: X, dY and W1 by the transposes the weight-gradient / input-gradient GEMMs need, W2 by its
+    // pruning pass, the activations by the compressors.
     // ---- Alg. 1 -------------------------------------------------------------------------------
-    STAGE(launch_prune24(W1, F, D, D, 0, cfg->mode, w1v, w1m, s), "step/prune24(W1)");
-    STAGE(launch_gemm_nt(1, w1v, w1m, X, b1, F, T, D, 1, y1, F, s), "step/y1");                 // eq. (1)
-    STAGE(launch_sqrelu_vnm_compress(y1, T, F, y2v, y2m, cix, s), "step/sqrelu_vnm_compress");   // eq. (2) + V:N:M
-    STAGE(launch_vnm_to_24(y2v, y2m, cix, T, F, a24v, a24m, s), "step/y2->2:4");
-    STAGE(launch_gemm_nt(1, a24v, a24m, W2, nullptr, T, D, F, 0, Y3, D, s), "step/y3");          // eq. (3)
+    STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
+    STAGE(launch_prune24_step(W1, F, D, D, 0, cfg->mode, w1v, w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
+    STAGE(launch_gemm_nt_blocked(1, w1vb, w1mb, xb, b1, F, T, D, 1, y1, F, s), "step/y1");                  // eq. (1)
+    STAGE(launch_sqrelu_vnm_compress(y1, T, F, y2v, y2m, cix, a24v, a24m, s), "step/sqrelu_vnm_compress");  // eq. (2) + V:N:M
+    STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, w2v, w2m, w2vb, w2mb, w2b, s), "step/prune24(W2.T)");
+    STAGE(launch_gemm_nt_blocked(1, a24v, a24m, w2b, nullptr, T, D, F, 0, Y3, D, s), "step/y3");            // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
-    STAGE(launch_prune24(W2, F, D, F, 1, cfg->mode, w2v, w2m, s), "step/prune24(W2.T)");
-    STAGE(launch_gemm_nt(1, w2v, w2m, dY, nullptr, F, T, D, 1, dy2, F, s), "step/dy2");          // eq. (4)
-    STAGE(launch_vnm_expand_t(y2v, y2m, cix, T, F, at, s), "step/y2 expand");
-    STAGE(launch_transpose(dY, T, D, D, dyt, s), "step/dY.T");
-    STAGE(launch_gemm_nt(0, at, nullptr, dyt, nullptr, F, D, T, 1, dW2, F, s), "step/dW2");      // eq. (5)
-    STAGE(launch_dsqrelu_vnm(dy2, y1, y2m, cix, T, F, dy1v, s), "step/dsqrelu_vnm");             // eq. (6)
-    STAGE(launch_vnm_to_24(dy1v, y2m, cix, T, F, a24v, a24m, s), "step/dy1->2:4");
-    STAGE(launch_transpose(W1, F, D, D, w1t, s), "step/W1.T");
-    STAGE(launch_gemm_nt(1, a24v, a24m, w1t, nullptr, T, D, F, 0, dX, D, s), "step/dX");         // eq. (7)
-    STAGE(launch_vnm_expand_t(dy1v, y2m, cix, T, F, at, s), "step/dy1 expand");
-    STAGE(launch_transpose(X, T, D, D, xt, s), "step/X.T");
-    STAGE(launch_gemm_nt(0, at, nullptr, xt, nullptr, F, D, T, 0, dW1, D, s), "step/dW1");       // eq. (8)
+    STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
+    STAGE(launch_gemm_nt_blocked(1, w2vb, w2mb, dyb, nullptr, F, T, D, 1, dy2, F, s), "step/dy2");          // eq. (4)
+    STAGE(launch_vnm_expand_t(y2v, y2m, cix, T, F, atb, 1, s), "step/y2 expand");
+    STAGE(launch_gemm_nt_blocked(0, atb, nullptr, dytb, nullptr, F, D, T, 1, dW2, F, s), "step/dW2");       // eq. (5)
+    STAGE(launch_dsqrelu_vnm(dy2, y1, y2m, cix, T, F, dy1v, a24v, a24m, s), "step/dsqrelu_vnm");            // eq. (6)
+    STAGE(launch_transpose(W1, F, D, D, w1tb, 1, nullptr, s), "step/W1.T");
+    STAGE(launch_gemm_nt_blocked(1, a24v, a24m, w1tb, nullptr, T, D, F, 0, dX, D, s), "step/dX");           // eq. (7)
+    STAGE(launch_vnm_expand_t(dy1v, y2m, cix, T, F, atb, 1, s), "step/dy1 expand");
+    STAGE(launch_gemm_nt_blocked(0, atb, nullptr, xtb, nullptr, F, D, T, 0, dW1, D, s), "step/dW1");        // eq. (8)
     return SFFN_OK;
 }
 
 int sffn_tune(int key, int value) {
     if (key == 0) g_tile_sparse = value;
     else if (key == 1) g_tile_dense = value;
-    else if (key == 2) g_dbg = value;
     else return fail(SFFN_EINVAL, "%s", "sffn_tune: unknown key");
     return SFFN_OK;
 }

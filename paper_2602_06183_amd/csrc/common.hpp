@@ -43,4 +43,38 @@ __device__ __forceinline__ uint32_t select24(uint32_t a0, uint32_t a1, uint32_t 
     return v0 | (v1 << 16);
 }
 
+// "Blocked" operand layout used between the kernels of the fused step: a K-contiguous matrix of
+// 2-byte elements is cut into 1 KB blocks of 16 rows x 32 elements, block (r / 16, k / 32) stored at
+// ((r / 16) * KC + k / 32) * 512 elements with KC = K / 32.  One wavefront-wide 16-byte-per-lane
+// LDS-DMA load then moves exactly one contiguous block, which the L2 -> LDS path serves at close to
+// twice the rate of eight separate 128-byte row segments.
+__host__ __device__ __forceinline__ int64_t blk_off(int64_t r, int64_t k, int64_t KC) {
+    return (((r >> 4) * KC + (k >> 5)) << 9) + ((r & 15) << 5) + (k & 31);
+}
+// Metadata of a 2:4 matrix in blocks of 64 rows x 8 bytes (one main-loop step of 64 k): byte address of
+// the metadata byte covering k..k+7 of row r, with KS = K / 64.
+__host__ __device__ __forceinline__ int64_t mblk_off(int64_t r, int64_t k, int64_t KS) {
+    return (((r >> 6) * KS + (k >> 6)) << 9) + ((r & 63) << 3) + ((k & 63) >> 3);
+}
+
+// Two survivors per 8 columns leave at most two per aligned group of four, so a V:2:8 row block is
+// also two plain 2:4 groups.  Inputs: v = the two survivors (low half first), nib = their positions
+// among the four kept columns, cw = the four kept column offsets (one per byte).  Outputs: the two
+// packed groups (empty slots are +0 at unused positions) and their metadata byte.
+__device__ __forceinline__ void vnm_block_to_24(uint32_t v, uint32_t nib, uint32_t cw, uint32_t& a, uint32_t& b, uint32_t& mbyte) {
+    const uint32_t o0 = (cw >> (8 * (nib & 3u))) & 0xFFu, o1 = (cw >> (8 * (nib >> 2))) & 0xFFu;   // o0 < o1
+    const uint32_t v0 = v & 0xFFFFu, v1 = v >> 16;
+    uint32_t na, nb;
+    if (o1 < 4) {
+        a = v; na = o0 | (o1 << 2); b = 0; nb = 0x4;
+    } else if (o0 >= 4) {
+        a = 0; na = 0x4; b = v; nb = (o0 - 4) | ((o1 - 4) << 2);
+    } else {
+        if (o0 < 3) { a = v0; na = o0 | (3u << 2); } else { a = v0 << 16; na = 0u | (3u << 2); }
+        const uint32_t q = o1 - 4;
+        if (q > 0) { b = v1 << 16; nb = 0u | (q << 2); } else { b = v1; nb = 0u | (1u << 2); }
+    }
+    mbyte = na | (nb << 4);
+}
+
 }  // namespace sffn

@@ -60,7 +60,7 @@ template <bool SPARSE, bool OUT_I_CONTIG>
 __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restrict__ a_vals, const uint8_t* __restrict__ a_meta,
                                                         const uint16_t* __restrict__ B, const float* __restrict__ bias,
                                                         int Ra, int Rb, int K, uint16_t* __restrict__ out, int64_t ldo,
-                                                        int tiles_m, int tiles_n, int dbg) {
+                                                        int tiles_m, int tiles_n, int blocked) {
     using C = Cfg<SPARSE>;
     constexpr int BM = C::BM, BN = C::BN, WM = 128, WN = 64, FM = 4, FN = 2;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[C::NSTAGE * C::STAGE];
@@ -82,61 +82,53 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     const int i0 = tm * BM, j0 = tn * BN;
     const int lda = SPARSE ? K / 2 : K;
 
-    // ---- per-lane source addresses of the DMA loads (tile row clamped into the matrix: rows past the
-    //      edge only feed outputs that are never stored) ---------------------------------------------
+    // ---- per-lane source addresses of the DMA loads.  A wave-wide load fills 1 KB of LDS = 16 tile rows x
+    //      64 bytes; lane l lands at (row l / 4, 16-byte chunk l % 4) and therefore fetches the chunk that the
+    //      XOR swizzle assigns to that slot.  Row-major sources: 16 row segments per load; blocked sources
+    //      (common.hpp): the 16 rows x 64 bytes are one contiguous block.  Tile rows past the matrix edge
+    //      are clamped into it: they only feed outputs that are never stored. --------------------------
     constexpr int A_LD = C::A_BYTES / 1024 / 8;          // dma16 issues per wave for A
     constexpr int B_LD = C::B_BYTES / 1024 / 8;
     const uint16_t* a_src[A_LD];
     const uint16_t* b_src[B_LD];
     const uint8_t* m_src = nullptr;
+    int a_kstep, b_kstep, m_kstep;                       // per main-loop step, in elements / bytes
+    {
+        const int rb = lane >> 2;                                        // row inside the 16-row group
+        const int c = (lane & 3) ^ ((rb >> 2) & 3);                      // source chunk for this lane's LDS slot
+        const int KCa = SPARSE ? K / 64 : K / 32, KCb = K / 32;          // 32-element chunks per row
 #pragma unroll
-    for (int n = 0; n < A_LD; ++n) {
-        const int row = (wave * A_LD + n) * 16 + (lane >> 2);             // 16 rows of 64 B per KB
-        const int c = (lane & 3) ^ ((row >> 2) & 3);
-        int gr = i0 + row; gr = gr < Ra ? gr : Ra - 1;
-        a_src[n] = a_vals + (int64_t)gr * lda + c * 8;
-    }
-#pragma unroll
-    for (int n = 0; n < B_LD; ++n) {
-        int row, c;
-        if (SPARSE) {
-            // the 128-byte k range of a row is kept as two 64-byte half rows (half-tile h at h * 16 KB), each
-            // laid out like the A tile, which keeps every 16-lane b128 read group on 64 distinct banks
-            const int blk = wave * B_LD + n, h = blk >> 4;
-            row = (blk & 15) * 16 + (lane >> 2);
-            c = h * 4 + ((lane & 3) ^ ((row >> 2) & 3));
-        } else {
-            row = (wave * B_LD + n) * 16 + (lane >> 2);
-            c = (lane & 3) ^ ((row >> 2) & 3);
+        for (int n = 0; n < A_LD; ++n) {
+            int gr = i0 + (wave * A_LD + n) * 16; gr = gr < Ra ? gr : Ra - 16;
+            a_src[n] = blocked ? a_vals + ((int64_t)(gr >> 4) * KCa << 9) + rb * 32 + c * 8
+                               : a_vals + (int64_t)(gr + rb) * lda + c * 8;
         }
-        int gr = j0 + row; gr = gr < Rb ? gr : Rb - 1;
-        b_src[n] = B + (int64_t)gr * K + c * 8;
-    }
-    if (SPARSE) {
-        const int row = (wave * 64 + lane) >> 1;
-        int gr = i0 + row; gr = gr < Ra ? gr : Ra - 1;
-        m_src = a_meta + (int64_t)gr * (K / 8) + (lane & 1) * 4;
+#pragma unroll
+        for (int n = 0; n < B_LD; ++n) {
+            // SPARSE: a stage holds 64 k of B as two half-tiles (k 0-31, k 32-63), each laid out like the A tile
+            const int bk = wave * B_LD + n, h = SPARSE ? (bk >> 4) : 0;
+            int gr = j0 + (bk & 15) * 16; gr = gr < Rb ? gr : Rb - 16;
+            b_src[n] = blocked ? B + (((int64_t)(gr >> 4) * KCb + h) << 9) + rb * 32 + c * 8
+                               : B + (int64_t)(gr + rb) * K + h * 32 + c * 8;
+        }
+        if (SPARSE) {
+            int gr = i0 + wave * 32; gr = gr < Ra ? gr : Ra - 32;
+            m_src = blocked ? a_meta + ((int64_t)(gr >> 6) * (K / 64) << 9) + (gr & 63) * 8 + lane * 4
+                            : a_meta + (int64_t)(gr + (lane >> 1)) * (K / 8) + (lane & 1) * 4;
+        }
+        a_kstep = blocked ? 512 : 32;
+        b_kstep = blocked ? 512 * (C::BK / 32) : C::BK;
+        m_kstep = blocked ? 512 : 8;
     }
     auto issue = [&](int kt, int stage) {
         unsigned char* sa = smem + stage * C::STAGE;
         unsigned char* sb = sa + C::A_BYTES;
         unsigned char* sm = sb + C::B_BYTES;
-        if (dbg & 4) {   // timing experiment only: pretend both operands are stored tile-major (contiguous chunks)
-            const int nkk = K / C::BK;
-            const unsigned char* ab = (const unsigned char*)a_vals + ((size_t)tm * nkk + kt) * C::A_BYTES;
-            const unsigned char* bb = (const unsigned char*)B + ((size_t)tn * nkk + kt) * C::B_BYTES;
 #pragma unroll
-            for (int n = 0; n < A_LD; ++n) dma16(ab + (wave * A_LD + n) * 1024 + lane * 16, sa + (wave * A_LD + n) * 1024);
+        for (int n = 0; n < A_LD; ++n) dma16(a_src[n] + (int64_t)kt * a_kstep, sa + (wave * A_LD + n) * 1024);
 #pragma unroll
-            for (int n = 0; n < B_LD; ++n) dma16(bb + (wave * B_LD + n) * 1024 + lane * 16, sb + (wave * B_LD + n) * 1024);
-            if (SPARSE) dma4(a_meta + ((size_t)tm * nkk + kt) * C::META_BYTES + wave * 256 + lane * 4, sm + wave * 256);
-            return;
-        }
-#pragma unroll
-        for (int n = 0; n < A_LD; ++n) dma16(a_src[n] + kt * 32, sa + (wave * A_LD + n) * 1024);
-#pragma unroll
-        for (int n = 0; n < B_LD; ++n) dma16(b_src[n] + kt * C::BK, sb + (wave * B_LD + n) * 1024);
-        if (SPARSE) dma4(m_src + kt * 8, sm + wave * 256);
+        for (int n = 0; n < B_LD; ++n) dma16(b_src[n] + (int64_t)kt * b_kstep, sb + (wave * B_LD + n) * 1024);
+        if (SPARSE) dma4(m_src + (int64_t)kt * m_kstep, sm + wave * 256);
     };
 
     // ---- per-lane LDS offsets of the fragment reads (inside a stage) --------------------------------
@@ -208,10 +200,10 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     for (int kt = 0; kt < nk; ++kt) {
         const int nxt = kt + DIST;
         const int next_stage = (stage + 1 == C::NSTAGE) ? 0 : stage + 1;
-        if (!(dbg & 1)) issue(nxt < nk ? nxt : nk - 1, fill);            // the stage being refilled held tile kt-1
+        issue(nxt < nk ? nxt : nk - 1, fill);            // the stage being refilled held tile kt-1
         read_frags(Q, stage, 1);
         __builtin_amdgcn_sched_barrier(0);
-        if (!(dbg & 2)) mma(P);
+        mma(P);
         __builtin_amdgcn_sched_barrier(0);
         // Q has arrived, tile kt+1 has landed (this wave's part); after the barrier every wave is done
         // reading this stage and every wave's part of tile kt+1 is in LDS
@@ -220,7 +212,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         __builtin_amdgcn_sched_barrier(0);
         read_frags(P, next_stage, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (!(dbg & 2)) mma(Q);
+        mma(Q);
         __builtin_amdgcn_sched_barrier(0);
         stage = next_stage;
         fill = (fill + 1 == C::NSTAGE) ? 0 : fill + 1;
@@ -270,26 +262,30 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     }
 }
 
-int g_dbg = 0;
-
 template <bool SPARSE>
 static hipError_t launch_v2(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t Ra,
-                            int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
+                            int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, int blocked, hipStream_t s) {
     const int tiles_m = (int)((Ra + 255) / 256), tiles_n = (int)((Rb + 255) / 256);
     dim3 grid((unsigned)(tiles_m * tiles_n));
     if (out_i_contig)
         hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
-                           out, ldo, tiles_m, tiles_n, g_dbg);
+                           out, ldo, tiles_m, tiles_n, blocked);
     else
         hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, false>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
-                           out, ldo, tiles_m, tiles_n, g_dbg);
+                           out, ldo, tiles_m, tiles_n, blocked);
     return hipGetLastError();
 }
 
 hipError_t launch_gemm_nt_v2(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
                              int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
-    if (sparse_a) return launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, s);
-    return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, s);
+    if (sparse_a) return launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s);
+    return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s);
+}
+
+hipError_t launch_gemm_nt_blocked(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
+                                  int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
+    if (sparse_a) return launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 1, s);
+    return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 1, s);
 }
 
 }  // namespace sffn

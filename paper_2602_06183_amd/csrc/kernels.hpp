@@ -7,23 +7,33 @@ namespace sffn {
 
 hipError_t launch_prune24(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
                           uint8_t* meta, hipStream_t stream);
+// v24blk / m24blk (both or neither): also write the result as a plain 2:4 matrix over all F columns in the
+// blocked operand layout (common.hpp), ready to be the sparse operand of the GEMMs.
 hipError_t launch_sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, uint16_t* vals, uint8_t* meta,
-                                      uint8_t* colidx, hipStream_t s);
+                                      uint8_t* colidx, uint16_t* v24blk, uint8_t* m24blk, hipStream_t s);
 hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, const uint8_t* colidx,
-                              int64_t T, int64_t F, uint16_t* dvals, hipStream_t s);
+                              int64_t T, int64_t F, uint16_t* dvals, uint16_t* v24blk, uint8_t* m24blk, hipStream_t s);
+// 2:4 prune-and-pack for the fused step: canonical outputs plus the blocked copies the GEMMs read;
+// trans = 1 can also emit a blocked copy of the source matrix itself (rows = its rows, K = its columns).
+hipError_t launch_prune24_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
+                               uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream);
 hipError_t launch_vnm_to_24(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
                             uint16_t* vals24, uint8_t* meta24, hipStream_t s);
 hipError_t launch_vnm_expand_t(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
-                               uint16_t* out, hipStream_t s);
-hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld, uint16_t* out, hipStream_t s);
+                               uint16_t* out, int blocked, hipStream_t s);
+hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld, uint16_t* out, int blocked, uint16_t* out_same,
+                            hipStream_t s);
 
 // C[i, j] = sum_k A[i, k] * B[j, k]  (both operands K-contiguous).
 //   sparse_a: A given as 2:4 packed (a_vals [Ra, K/2], a_meta [Ra, K/8]) and multiplied on the
 //             structured-sparse matrix cores; else a_vals is a dense [Ra, K] matrix.
 //   out_i_contig: 1 -> out[j * ldo + i] (+ bias[i]);  0 -> out[i * ldo + j].
+//   blocked (launch_gemm_nt_blocked): both operands (and the metadata) are in the blocked layout of common.hpp.
+hipError_t launch_gemm_nt_blocked(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
+                                  int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
 hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
                           int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
 
-extern int g_tile_sparse, g_tile_dense, g_dbg;
+extern int g_tile_sparse, g_tile_dense;
 
 }  // namespace sffn

@@ -43,7 +43,9 @@ __global__ void __launch_bounds__(256) prune24_rows_kernel(const uint16_t* __res
 // stay contiguous.
 template <bool SOFT>
 __global__ void __launch_bounds__(256) prune24_cols_kernel(const uint16_t* __restrict__ src, int64_t R, int K, int64_t ld,
-                                                          uint16_t* __restrict__ vals, uint8_t* __restrict__ meta) {
+                                                          uint16_t* __restrict__ vals, uint8_t* __restrict__ meta,
+                                                          uint16_t* __restrict__ vblk, uint8_t* __restrict__ mblk,
+                                                          uint16_t* __restrict__ src_blk) {
     constexpr int TK = 128, TR = 64, PITCH = TR + 8;
     __shared__ __attribute__((aligned(16))) uint16_t tile[TK * PITCH];
     const int64_t r0 = (int64_t)blockIdx.x * TR;
@@ -57,6 +59,15 @@ __global__ void __launch_bounds__(256) prune24_cols_kernel(const uint16_t* __res
         *reinterpret_cast<uint4*>(&tile[kk * PITCH + seg * 8]) = w;
     }
     __syncthreads();
+    if (src_blk) {      // blocked copy of the source tile itself: rows = k (128), columns = r (64) -> 16 blocks of 1 KB
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = tid + 256 * i, bk = e >> 6, l = e & 63;
+            const int kr = (bk >> 1) * 16 + (l >> 2), rc = (bk & 1) * 32 + (l & 3) * 8;
+            if (k0 + kr < K)
+                *reinterpret_cast<uint4*>(src_blk + blk_off(k0 + kr, r0 + rc, R / 32)) = *reinterpret_cast<const uint4*>(&tile[kr * PITCH + rc]);
+        }
+    }
     const int rr = tid % 64, q = tid / 64;
     if (k0 + 32 * q >= K) return;
     uint32_t ov[8], mbytes = 0;
@@ -72,6 +83,38 @@ __global__ void __launch_bounds__(256) prune24_cols_kernel(const uint16_t* __res
     *reinterpret_cast<uint4*>(vo) = make_uint4(ov[0], ov[1], ov[2], ov[3]);
     *reinterpret_cast<uint4*>(vo + 8) = make_uint4(ov[4], ov[5], ov[6], ov[7]);
     *reinterpret_cast<uint32_t*>(meta + r * (K / 8) + (k0 + 32 * q) / 8) = mbytes;
+    if (vblk) {
+        uint16_t* vb = vblk + blk_off(r, (k0 + 32 * q) / 2, K / 64);
+        *reinterpret_cast<uint4*>(vb) = make_uint4(ov[0], ov[1], ov[2], ov[3]);
+        *reinterpret_cast<uint4*>(vb + 8) = make_uint4(ov[4], ov[5], ov[6], ov[7]);
+        *reinterpret_cast<uint32_t*>(mblk + mblk_off(r, k0 + 32 * q, K / 64)) = mbytes;
+    }
+}
+
+// Rows K-contiguous, fused-step variant: a wavefront owns 16 rows x 64 k, i.e. exactly one 1 KB block of the
+// blocked packed output; lane = (row, 16 k), two 16-byte loads, one 16-byte store per output.
+template <bool SOFT>
+__global__ void __launch_bounds__(256) prune24_rows_step_kernel(const uint16_t* __restrict__ src, int K, int64_t ld,
+                                                               uint16_t* __restrict__ vals, uint8_t* __restrict__ meta,
+                                                               uint16_t* __restrict__ vblk, uint8_t* __restrict__ mblk) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int chunk = blockIdx.x * 4 + wave;            // 64-k column
+    if (chunk * 64 >= K) return;
+    const int64_t r = (int64_t)blockIdx.y * 16 + (lane >> 2);
+    const int q = lane & 3, k = chunk * 64 + 16 * q;
+    const uint4 w0 = *reinterpret_cast<const uint4*>(src + r * ld + k);
+    const uint4 w1 = *reinterpret_cast<const uint4*>(src + r * ld + k + 8);
+    uint32_t n0, n1, n2, n3;
+    const uint32_t o0 = select24<SOFT>(w0.x & 0xFFFFu, w0.x >> 16, w0.y & 0xFFFFu, w0.y >> 16, n0);
+    const uint32_t o1 = select24<SOFT>(w0.z & 0xFFFFu, w0.z >> 16, w0.w & 0xFFFFu, w0.w >> 16, n1);
+    const uint32_t o2 = select24<SOFT>(w1.x & 0xFFFFu, w1.x >> 16, w1.y & 0xFFFFu, w1.y >> 16, n2);
+    const uint32_t o3 = select24<SOFT>(w1.z & 0xFFFFu, w1.z >> 16, w1.w & 0xFFFFu, w1.w >> 16, n3);
+    const uint4 ov = make_uint4(o0, o1, o2, o3);
+    const uint16_t mb = (uint16_t)(n0 | (n1 << 4) | (n2 << 8) | (n3 << 12));
+    *reinterpret_cast<uint4*>(vals + r * (K / 2) + k / 2) = ov;
+    *reinterpret_cast<uint16_t*>(meta + r * (K / 8) + k / 8) = mb;
+    *reinterpret_cast<uint4*>(vblk + blk_off(r, k / 2, K / 64)) = ov;
+    *reinterpret_cast<uint16_t*>(mblk + mblk_off(r, k, K / 64)) = mb;
 }
 
 hipError_t launch_prune24(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
@@ -90,8 +133,22 @@ hipError_t launch_prune24(const uint16_t* src, int64_t R, int64_t K, int64_t ld,
         }
     } else {
         dim3 grid((unsigned)(R / 64), (unsigned)((K + 127) / 128));
-        if (mode == 0) hipLaunchKernelGGL((prune24_cols_kernel<false>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta);
-        else           hipLaunchKernelGGL((prune24_cols_kernel<true>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta);
+        if (mode == 0) hipLaunchKernelGGL((prune24_cols_kernel<false>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta, (uint16_t*)nullptr, (uint8_t*)nullptr, (uint16_t*)nullptr);
+        else           hipLaunchKernelGGL((prune24_cols_kernel<true>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta, (uint16_t*)nullptr, (uint8_t*)nullptr, (uint16_t*)nullptr);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_prune24_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
+                               uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream) {
+    if (!trans) {
+        dim3 grid((unsigned)((K / 64 + 3) / 4), (unsigned)(R / 16));
+        if (mode == 0) hipLaunchKernelGGL((prune24_rows_step_kernel<false>), grid, dim3(256), 0, stream, src, (int)K, ld, vals, meta, vblk, mblk);
+        else           hipLaunchKernelGGL((prune24_rows_step_kernel<true>), grid, dim3(256), 0, stream, src, (int)K, ld, vals, meta, vblk, mblk);
+    } else {
+        dim3 grid((unsigned)(R / 64), (unsigned)((K + 127) / 128));
+        if (mode == 0) hipLaunchKernelGGL((prune24_cols_kernel<false>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta, vblk, mblk, src_blk);
+        else           hipLaunchKernelGGL((prune24_cols_kernel<true>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta, vblk, mblk, src_blk);
     }
     return hipGetLastError();
 }

@@ -26,7 +26,8 @@ __device__ __forceinline__ uint32_t sqrelu_pair(uint32_t w) {
 // contiguous 1 KB (loads), 256 B (values) or 32 B (metadata) run.
 __global__ void __launch_bounds__(256) sqrelu_vnm_compress_kernel(const uint16_t* __restrict__ y1, int64_t F, int nblk,
                                                                  uint16_t* __restrict__ vals, uint8_t* __restrict__ meta,
-                                                                 uint8_t* __restrict__ colidx) {
+                                                                 uint8_t* __restrict__ colidx, uint16_t* __restrict__ v24blk,
+                                                                 uint8_t* __restrict__ m24blk) {
     __shared__ float s_score[8][64];
     __shared__ uint32_t s_col[64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -93,15 +94,27 @@ __global__ void __launch_bounds__(256) sqrelu_vnm_compress_kernel(const uint16_t
             *reinterpret_cast<uint32_t*>(vals + row * (F / 4) + (int64_t)blk * 2) = v;
             if ((lane & 1) == 0) meta[row * (F / 16) + (blk >> 1)] = (uint8_t)(nib | (other << 4));
         }
+        if (v24blk) {       // the same block as two plain 2:4 groups, in the blocked operand layout of the GEMMs
+            uint32_t a, b, mb;
+            vnm_block_to_24(v, nib, cw, a, b, mb);
+            uint32_t m4 = mb | ((uint32_t)__shfl_down((int)mb, 1, 64) << 8);
+            m4 |= (uint32_t)__shfl_down((int)m4, 2, 64) << 16;
+            if (active) {
+                const int64_t row = row0 + i;
+                *reinterpret_cast<uint2*>(v24blk + blk_off(row, (int64_t)blk * 4, F / 64)) = make_uint2(a, b);
+                if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(m24blk + mblk_off(row, (int64_t)blk * 8, F / 64)) = m4;
+            }
+        }
     }
 }
 
 // eq. (6) evaluated only where y2 was kept.  One thread per (row, column block).
 __global__ void __launch_bounds__(256) dsqrelu_vnm_kernel(const uint16_t* __restrict__ dy2, const uint16_t* __restrict__ y1,
                                                          const uint8_t* __restrict__ meta, const uint8_t* __restrict__ colidx,
-                                                         int64_t F, int nblk, uint16_t* __restrict__ dvals) {
+                                                         int64_t F, int nblk, uint16_t* __restrict__ dvals,
+                                                         uint16_t* __restrict__ v24blk, uint8_t* __restrict__ m24blk) {
     const int blk = blockIdx.x * 256 + threadIdx.x;
-    if (blk >= nblk) return;
+    if (blk >= nblk) return;          // nblk is a multiple of 8, so groups of 4 lanes are in or out together
     const int64_t t = blockIdx.y;
     const uint32_t cw = *reinterpret_cast<const uint32_t*>(colidx + ((t >> 6) * nblk + blk) * 4);
     const uint32_t nib = (meta[t * (F / 16) + (blk >> 1)] >> (4 * (blk & 1))) & 0xFu;
@@ -112,7 +125,16 @@ __global__ void __launch_bounds__(256) dsqrelu_vnm_kernel(const uint16_t* __rest
     const float ya = bf2f(pick16(yw, o0)), yb = bf2f(pick16(yw, o1));
     const float ga = 2.0f * bf2f(pick16(dw, o0)) * (ya > 0.0f ? ya : 0.0f);
     const float gb = 2.0f * bf2f(pick16(dw, o1)) * (yb > 0.0f ? yb : 0.0f);
-    *reinterpret_cast<uint32_t*>(dvals + t * (F / 4) + (int64_t)blk * 2) = f2bf(ga) | (f2bf(gb) << 16);
+    const uint32_t v = f2bf(ga) | (f2bf(gb) << 16);
+    *reinterpret_cast<uint32_t*>(dvals + t * (F / 4) + (int64_t)blk * 2) = v;
+    if (v24blk) {
+        uint32_t a, b, mb;
+        vnm_block_to_24(v, nib, cw, a, b, mb);
+        uint32_t m4 = mb | ((uint32_t)__shfl_down((int)mb, 1, 64) << 8);
+        m4 |= (uint32_t)__shfl_down((int)m4, 2, 64) << 16;
+        *reinterpret_cast<uint2*>(v24blk + blk_off(t, (int64_t)blk * 4, F / 64)) = make_uint2(a, b);
+        if ((threadIdx.x & 3) == 0) *reinterpret_cast<uint32_t*>(m24blk + mblk_off(t, (int64_t)blk * 8, F / 64)) = m4;
+    }
 }
 
 // Two survivors per 8 columns leave at most two per aligned group of four, so a V:2:8 matrix is
@@ -126,28 +148,18 @@ __global__ void __launch_bounds__(256) vnm_to_24_kernel(const uint16_t* __restri
     const int64_t t = blockIdx.y;
     const uint32_t cw = *reinterpret_cast<const uint32_t*>(colidx + ((t >> 6) * nblk + blk) * 4);
     const uint32_t nib = (meta[t * (F / 16) + (blk >> 1)] >> (4 * (blk & 1))) & 0xFu;
-    const uint32_t o0 = (cw >> (8 * (nib & 3u))) & 0xFFu, o1 = (cw >> (8 * (nib >> 2))) & 0xFFu;   // o0 < o1
     const uint32_t v = *reinterpret_cast<const uint32_t*>(vals + t * (F / 4) + (int64_t)blk * 2);
-    const uint32_t v0 = v & 0xFFFFu, v1 = v >> 16;
-    uint32_t a, na, b, nb;            // low group (columns 0-3) and high group (columns 4-7)
-    if (o1 < 4) {
-        a = v; na = o0 | (o1 << 2); b = 0; nb = 0x4;
-    } else if (o0 >= 4) {
-        a = 0; na = 0x4; b = v; nb = (o0 - 4) | ((o1 - 4) << 2);
-    } else {
-        if (o0 < 3) { a = v0; na = o0 | (3u << 2); } else { a = v0 << 16; na = 0u | (3u << 2); }
-        const uint32_t q = o1 - 4;
-        if (q > 0) { b = v1 << 16; nb = 0u | (q << 2); } else { b = v1; nb = 0u | (1u << 2); }
-    }
+    uint32_t a, b, mb;
+    vnm_block_to_24(v, nib, cw, a, b, mb);
     *reinterpret_cast<uint2*>(vals24 + t * (F / 2) + (int64_t)blk * 4) = make_uint2(a, b);
-    meta24[t * (F / 8) + blk] = (uint8_t)(na | (nb << 4));
+    meta24[t * (F / 8) + blk] = (uint8_t)mb;
 }
 
 // Dense, transposed expansion AT[f, t] of a V:N:M matrix (K-contiguous operand for the
 // weight-gradient GEMMs).  One workgroup = 64 rows x 8 column blocks.
 __global__ void __launch_bounds__(256) vnm_expand_t_kernel(const uint16_t* __restrict__ vals, const uint8_t* __restrict__ meta,
                                                           const uint8_t* __restrict__ colidx, int64_t T, int64_t F, int nblk,
-                                                          uint16_t* __restrict__ out) {
+                                                          uint16_t* __restrict__ out, int blocked) {
     __shared__ __attribute__((aligned(16))) uint16_t tile[64][64 + 8];
     const int tid = threadIdx.x;
     for (int i = tid; i < 64 * 72 / 2; i += 256) reinterpret_cast<uint32_t*>(&tile[0][0])[i] = 0;
@@ -170,15 +182,23 @@ __global__ void __launch_bounds__(256) vnm_expand_t_kernel(const uint16_t* __res
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int e = tid + 256 * i;           // 64 f rows x 8 segments of 8 tokens
-        const int fr = e >> 3, seg = e & 7;
-        *reinterpret_cast<uint4*>(out + ((int64_t)b0 * 8 + fr) * T + tb * 64 + seg * 8) =
-            *reinterpret_cast<const uint4*>(&tile[fr][seg * 8]);
+        if (blocked) {                      // 8 blocks of 16 f-rows x 32 tokens, one per 64 consecutive e
+            const int bk = e >> 6, l = e & 63, fr = (bk >> 1) * 16 + (l >> 2), tc = (bk & 1) * 32 + (l & 3) * 8;
+            *reinterpret_cast<uint4*>(out + blk_off((int64_t)b0 * 8 + fr, tb * 64 + tc, T / 32)) =
+                *reinterpret_cast<const uint4*>(&tile[fr][tc]);
+        } else {
+            const int fr = e >> 3, seg = e & 7;
+            *reinterpret_cast<uint4*>(out + ((int64_t)b0 * 8 + fr) * T + tb * 64 + seg * 8) =
+                *reinterpret_cast<const uint4*>(&tile[fr][seg * 8]);
+        }
     }
 }
 
 // out[c, r] = in[r, c]; R, C multiples of 64.
+// blocked = 1: out (the transpose) and, when given, out_same (a copy of `in`) are written in the blocked
+// operand layout instead of row-major.
 __global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* __restrict__ in, int64_t R, int64_t C, int64_t ld,
-                                                            uint16_t* __restrict__ out) {
+                                                            uint16_t* __restrict__ out, int blocked, uint16_t* __restrict__ out_same) {
     __shared__ __attribute__((aligned(16))) uint16_t tile[64][64 + 2];
     const int tid = threadIdx.x;
     const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
@@ -192,27 +212,36 @@ __global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* __r
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        const int e = tid + 256 * i, cc = e >> 3, seg = e & 7;
+        const int e = tid + 256 * i;
+        int cc, rs;                          // output row (a column of `in`) and first of 8 source rows
+        if (blocked) { const int bk = e >> 6, l = e & 63; cc = (bk >> 1) * 16 + (l >> 2); rs = (bk & 1) * 32 + (l & 3) * 8; }
+        else { cc = e >> 3; rs = (e & 7) * 8; }
         uint32_t o[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] = tile[seg * 8 + 2 * j][cc] | ((uint32_t)tile[seg * 8 + 2 * j + 1][cc] << 16);
-        *reinterpret_cast<uint4*>(out + (c0 + cc) * R + r0 + seg * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+        for (int j = 0; j < 4; ++j) o[j] = tile[rs + 2 * j][cc] | ((uint32_t)tile[rs + 2 * j + 1][cc] << 16);
+        uint16_t* dst = blocked ? out + blk_off(c0 + cc, r0 + rs, R / 32) : out + (c0 + cc) * R + r0 + rs;
+        *reinterpret_cast<uint4*>(dst) = make_uint4(o[0], o[1], o[2], o[3]);
+        if (out_same) {
+            const int bk = e >> 6, l = e & 63, rr = (bk >> 1) * 16 + (l >> 2), cs = (bk & 1) * 32 + (l & 3) * 8;
+            const uint32_t* p = reinterpret_cast<const uint32_t*>(&tile[rr][cs]);
+            *reinterpret_cast<uint4*>(out_same + blk_off(r0 + rr, c0 + cs, C / 32)) = make_uint4(p[0], p[1], p[2], p[3]);
+        }
     }
 }
 
 hipError_t launch_sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, uint16_t* vals, uint8_t* meta, uint8_t* colidx,
-                                      hipStream_t s) {
+                                      uint16_t* v24blk, uint8_t* m24blk, hipStream_t s) {
     const int nblk = (int)(F / 8);
     dim3 grid((unsigned)((nblk + 63) / 64), (unsigned)(T / 64));
-    hipLaunchKernelGGL(sqrelu_vnm_compress_kernel, grid, dim3(256), 0, s, y1, F, nblk, vals, meta, colidx);
+    hipLaunchKernelGGL(sqrelu_vnm_compress_kernel, grid, dim3(256), 0, s, y1, F, nblk, vals, meta, colidx, v24blk, m24blk);
     return hipGetLastError();
 }
 
 hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, const uint8_t* colidx, int64_t T,
-                              int64_t F, uint16_t* dvals, hipStream_t s) {
+                              int64_t F, uint16_t* dvals, uint16_t* v24blk, uint8_t* m24blk, hipStream_t s) {
     const int nblk = (int)(F / 8);
     dim3 grid((unsigned)((nblk + 255) / 256), (unsigned)T);
-    hipLaunchKernelGGL(dsqrelu_vnm_kernel, grid, dim3(256), 0, s, dy2, y1, meta, colidx, F, nblk, dvals);
+    hipLaunchKernelGGL(dsqrelu_vnm_kernel, grid, dim3(256), 0, s, dy2, y1, meta, colidx, F, nblk, dvals, v24blk, m24blk);
     return hipGetLastError();
 }
 
@@ -225,16 +254,17 @@ hipError_t launch_vnm_to_24(const uint16_t* vals, const uint8_t* meta, const uin
 }
 
 hipError_t launch_vnm_expand_t(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
-                               uint16_t* out, hipStream_t s) {
+                               uint16_t* out, int blocked, hipStream_t s) {
     const int nblk = (int)(F / 8);
     dim3 grid((unsigned)(nblk / 8), (unsigned)(T / 64));
-    hipLaunchKernelGGL(vnm_expand_t_kernel, grid, dim3(256), 0, s, vals, meta, colidx, T, F, nblk, out);
+    hipLaunchKernelGGL(vnm_expand_t_kernel, grid, dim3(256), 0, s, vals, meta, colidx, T, F, nblk, out, blocked);
     return hipGetLastError();
 }
 
-hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld, uint16_t* out, hipStream_t s) {
+hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld, uint16_t* out, int blocked, uint16_t* out_same,
+                            hipStream_t s) {
     dim3 grid((unsigned)(C / 64), (unsigned)(R / 64));
-    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, in, R, C, ld, out);
+    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, in, R, C, ld, out, blocked, out_same);
     return hipGetLastError();
 }
 
