@@ -120,16 +120,23 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         b_kstep = blocked ? 512 * (C::BK / 32) : C::BK;
         m_kstep = blocked ? 512 : 8;
     }
-    auto issue = [&](int kt, int stage) {
+    // the DMA loads of one stage, issued in two halves (h = 0, 1) so that they can sit between matrix instructions
+    auto issue_half = [&](int kt, int stage, int h) {
         unsigned char* sa = smem + stage * C::STAGE;
         unsigned char* sb = sa + C::A_BYTES;
         unsigned char* sm = sb + C::B_BYTES;
+        if (h == 0) {
 #pragma unroll
-        for (int n = 0; n < A_LD; ++n) dma16(a_src[n] + (int64_t)kt * a_kstep, sa + (wave * A_LD + n) * 1024);
+            for (int n = 0; n < A_LD; ++n) dma16(a_src[n] + (int64_t)kt * a_kstep, sa + (wave * A_LD + n) * 1024);
 #pragma unroll
-        for (int n = 0; n < B_LD; ++n) dma16(b_src[n] + (int64_t)kt * b_kstep, sb + (wave * B_LD + n) * 1024);
-        if (SPARSE) dma4(m_src + (int64_t)kt * m_kstep, sm + wave * 256);
+            for (int n = 0; n < B_LD / 2; ++n) dma16(b_src[n] + (int64_t)kt * b_kstep, sb + (wave * B_LD + n) * 1024);
+        } else {
+#pragma unroll
+            for (int n = B_LD / 2; n < B_LD; ++n) dma16(b_src[n] + (int64_t)kt * b_kstep, sb + (wave * B_LD + n) * 1024);
+            if (SPARSE) dma4(m_src + (int64_t)kt * m_kstep, sm + wave * 256);
+        }
     };
+    auto issue = [&](int kt, int stage) { issue_half(kt, stage, 0); issue_half(kt, stage, 1); };
 
     // ---- per-lane LDS offsets of the fragment reads (inside a stage) --------------------------------
     int a_off[FM], b_off[FN], m_off[FM];
@@ -161,32 +168,33 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         Frag16 b16[FN];     // SPARSE: 16 k-values per lane
         Frag8 b8[FN];       // dense: 8 k-values per lane
     };
+    auto read_a = [&](FragSet& f, const unsigned char* st, int ks, int a) {
+        f.a[a].u = *reinterpret_cast<const uint4*>(st + (a_off[a] ^ (32 * ks)));
+        if (SPARSE) f.idx[a] = *reinterpret_cast<const uint16_t*>(st + m_off[a] + 4 * ks);
+    };
+    auto read_b = [&](FragSet& f, const unsigned char* st, int ks, int b) {
+        if (SPARSE) {
+            f.b16[b].u[0] = *reinterpret_cast<const uint4*>(st + b_off[b] + 16384 * ks);
+            f.b16[b].u[1] = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ 32) + 16384 * ks);
+        } else {
+            f.b8[b].u = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ (32 * ks)));
+        }
+    };
     auto read_frags = [&](FragSet& f, int stage, int ks) {
         const unsigned char* st = smem + stage * C::STAGE;
 #pragma unroll
-        for (int a = 0; a < FM; ++a) {
-            f.a[a].u = *reinterpret_cast<const uint4*>(st + (a_off[a] ^ (32 * ks)));
-            if (SPARSE) f.idx[a] = *reinterpret_cast<const uint16_t*>(st + m_off[a] + 4 * ks);
-        }
+        for (int a = 0; a < FM; ++a) read_a(f, st, ks, a);
+#pragma unroll
+        for (int b = 0; b < FN; ++b) read_b(f, st, ks, b);
+    };
+    auto mma_row = [&](const FragSet& f, int a) {
 #pragma unroll
         for (int b = 0; b < FN; ++b) {
-            if (SPARSE) {
-                f.b16[b].u[0] = *reinterpret_cast<const uint4*>(st + b_off[b] + 16384 * ks);
-                f.b16[b].u[1] = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ 32) + 16384 * ks);
-            } else {
-                f.b8[b].u = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ (32 * ks)));
-            }
+            if (SPARSE) acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[a].v, f.b16[b].v, acc[a][b], f.idx[a], 0, 0);
+            else        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a].v, f.b8[b].v, acc[a][b], 0, 0, 0);
         }
     };
-    auto mma = [&](const FragSet& f) {
-#pragma unroll
-        for (int a = 0; a < FM; ++a)
-#pragma unroll
-            for (int b = 0; b < FN; ++b) {
-                if (SPARSE) acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[a].v, f.b16[b].v, acc[a][b], f.idx[a], 0, 0);
-                else        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a].v, f.b8[b].v, acc[a][b], 0, 0, 0);
-            }
-    };
+#define SB() __builtin_amdgcn_sched_barrier(0)
 
     const int nk = K / C::BK;
     constexpr int DIST = C::NSTAGE - 1;
@@ -197,26 +205,37 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     FragSet P, Q;
     read_frags(P, 0, 0);
     int stage = 0, fill = DIST;
+    // One step = two halves of eight matrix instructions.  Each pair of matrix instructions (64+ cycles of
+    // the matrix pipe) is followed in program order by a few LDS reads for the other fragment set or by
+    // half of the next stage's DMA issue, so the non-matrix work of a wave hides behind its own MFMAs.
     for (int kt = 0; kt < nk; ++kt) {
-        const int nxt = kt + DIST;
+        const int nxt = (kt + DIST < nk) ? kt + DIST : nk - 1;
         const int next_stage = (stage + 1 == C::NSTAGE) ? 0 : stage + 1;
-        issue(nxt < nk ? nxt : nk - 1, fill);            // the stage being refilled held tile kt-1
-        read_frags(Q, stage, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(P);
-        __builtin_amdgcn_sched_barrier(0);
+        const unsigned char* st = smem + stage * C::STAGE;
+        const unsigned char* sn = smem + next_stage * C::STAGE;
+        mma_row(P, 0); SB();
+        read_a(Q, st, 1, 0); read_a(Q, st, 1, 1); read_b(Q, st, 1, 0); SB();
+        mma_row(P, 1); SB();
+        read_a(Q, st, 1, 2); read_a(Q, st, 1, 3); read_b(Q, st, 1, 1); SB();
+        mma_row(P, 2); SB();
+        issue_half(nxt, fill, 0); SB();                  // the stage being refilled held tile kt-1
+        mma_row(P, 3); SB();
+        issue_half(nxt, fill, 1); SB();
         // Q has arrived, tile kt+1 has landed (this wave's part); after the barrier every wave is done
         // reading this stage and every wave's part of tile kt+1 is in LDS
         __builtin_amdgcn_s_waitcnt(((DIST - 1) * C::LOADS & 0xF) | ((((DIST - 1) * C::LOADS) >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
         __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(P, next_stage, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(Q);
-        __builtin_amdgcn_sched_barrier(0);
+        SB();
+        mma_row(Q, 0); SB();
+        read_a(P, sn, 0, 0); read_a(P, sn, 0, 1); read_b(P, sn, 0, 0); SB();
+        mma_row(Q, 1); SB();
+        read_a(P, sn, 0, 2); read_a(P, sn, 0, 3); read_b(P, sn, 0, 1); SB();
+        mma_row(Q, 2); SB();
+        mma_row(Q, 3); SB();
         stage = next_stage;
         fill = (fill + 1 == C::NSTAGE) ? 0 : fill + 1;
     }
+#undef SB
     wait_vmcnt<0>();
     __syncthreads();
 
