@@ -240,21 +240,41 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     __syncthreads();
 
     if (OUT_I_CONTIG) {
+        // i is the contiguous output axis and a lane owns 4 consecutive i of one j.  Stage the wave's tile
+        // through LDS as [j][i] (two halves of 64 i) so that HBM sees 128-byte row segments instead of
+        // 16-byte ones; the bias (indexed by i) is added before the single rounding to bf16.
+        constexpr int EP = 64 * 2 + 16;
+        unsigned char* scratch = smem + wave * (WN * EP);
+        static_assert(8 * WN * EP <= C::NSTAGE * C::STAGE, "epilogue scratch must fit in the main-loop LDS");
 #pragma unroll
-        for (int a = 0; a < FM; ++a)
+        for (int h = 0; h < 2; ++h) {
 #pragma unroll
-            for (int b = 0; b < FN; ++b) {
-                const int j = j0 + wn * WN + b * 32 + l32;
+            for (int a2 = 0; a2 < 2; ++a2)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int i = i0 + wm * WM + a * 32 + 8 * g + 4 * lh;
-                    if (j < Rb && i < Ra) {
+                for (int b = 0; b < FN; ++b)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int a = 2 * h + a2;
+                        const int il = a2 * 32 + 8 * g + 4 * lh;              // i inside the 64-wide half
                         float v0 = acc[a][b][4 * g], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2], v3 = acc[a][b][4 * g + 3];
-                        if (bias) { const float4 bb = *reinterpret_cast<const float4*>(bias + i); v0 += bb.x; v1 += bb.y; v2 += bb.z; v3 += bb.w; }
-                        *reinterpret_cast<uint2*>(out + (int64_t)j * ldo + i) = make_uint2(f2bf(v0) | (f2bf(v1) << 16), f2bf(v2) | (f2bf(v3) << 16));
+                        if (bias) {
+                            int i = i0 + wm * WM + h * 64 + il; i = i < Ra ? i : Ra - 4;
+                            const float4 bb = *reinterpret_cast<const float4*>(bias + i);
+                            v0 += bb.x; v1 += bb.y; v2 += bb.z; v3 += bb.w;
+                        }
+                        *reinterpret_cast<uint2*>(scratch + (b * 32 + l32) * EP + il * 2) =
+                            make_uint2(f2bf(v0) | (f2bf(v1) << 16), f2bf(v2) | (f2bf(v3) << 16));
                     }
-                }
+            __syncthreads();
+#pragma unroll
+            for (int p = 0; p < WN / 8; ++p) {
+                const int row = p * 8 + (lane >> 3), ch = lane & 7;
+                const int j = j0 + wn * WN + row, i = i0 + wm * WM + h * 64 + ch * 8;
+                if (j < Rb && i < Ra)
+                    *reinterpret_cast<uint4*>(out + (int64_t)j * ldo + i) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
             }
+            __syncthreads();
+        }
     } else {
         constexpr int EP = WN * 2 + 16;
         unsigned char* scratch = smem + wave * (32 * EP);
