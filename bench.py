@@ -22,7 +22,7 @@ HBM_PEAK_GBS = 8000.0
 def algorithmic_flops(stage, T, D, F):
     """Multiply-adds the method itself needs (non-zero products), times two, per launch."""
     tdf = float(T) * D * F
-    return {"step/y1": tdf, "step/dy2": tdf,                      # 2:4 weights: half of K survives
+    return {"step/y1+sqrelu_vnm_compress": tdf, "step/dy2+dsqrelu_vnm": tdf,                      # 2:4 weights: half of K survives
             "step/y3": 0.5 * tdf, "step/dX": 0.5 * tdf,          # V:2:8 activations: a quarter survives
             "step/dW2": 0.5 * tdf, "step/dW1": 0.5 * tdf}.get(stage)
 
@@ -30,11 +30,11 @@ def algorithmic_flops(stage, T, D, F):
 def executed_flops(stage, T, D, F):
     """Flops the matrix cores are issued for (dense-equivalent of the instructions used)."""
     tdf = float(T) * D * F
-    return {"step/y1": 2 * tdf, "step/dy2": 2 * tdf, "step/y3": 2 * tdf, "step/dX": 2 * tdf,
+    return {"step/y1+sqrelu_vnm_compress": 2 * tdf, "step/dy2+dsqrelu_vnm": 2 * tdf, "step/y3": 2 * tdf, "step/dX": 2 * tdf,
             "step/dW2": 2 * tdf, "step/dW1": 2 * tdf}.get(stage)
 
 
-KERNEL_OF_STAGE = {"step/y1": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dy2": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
+KERNEL_OF_STAGE = {"step/y1+sqrelu_vnm_compress": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dy2+dsqrelu_vnm": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
                    "step/y3": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dX": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
                    "step/dW2": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>", "step/dW1": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>"}
 

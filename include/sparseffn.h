@@ -55,18 +55,25 @@ typedef struct sffn_cfg {
     int32_t V;      /* V:N:M block height, 64 */
     int32_t M;      /* V:N:M block width, 8 */
     int32_t mode;   /* SFFN_MODE_HARD or SFFN_MODE_SOFT for both weight sparsifiers */
-    int32_t reserved;
+    int32_t flags;  /* SFFN_FLAG_* */
 } sffn_cfg;
+
+/* ffn_sparse_step fuses eq. (2) + V:N:M compression into the epilogue of eq. (1) and eq. (6) into the
+ * epilogue of eq. (4), so the dense y1 and dy2 never have to reach HBM: the backward pass only needs y1 at
+ * y2's kept slots (y1_kept).  With this flag the step also stores the dense y1 and dy2 (same kernels, same
+ * arithmetic, two extra [T,F] writes), which is what lets a checker reproduce every stage bit for bit. */
+#define SFFN_FLAG_KEEP_DENSE 1
 
 /* Byte offsets, inside the workspace of ffn_sparse_step, of the tensors Alg. 2 line 1 saves
  * from the forward pass and of the other intermediates (all filled when the step returns). */
 typedef struct sffn_ws_layout {
     size_t w1_vals, w1_meta;        /* sparsify24(W1):   [F, D/2] bf16, [F, D/8] u8 */
     size_t w2t_vals, w2t_meta;      /* sparsify24(W2.T): [F, D/2] bf16, [F, D/8] u8 */
-    size_t y1;                      /* [T, F] bf16, eq. (1) plus bias */
+    size_t y1;                      /* [T, F] bf16, eq. (1) plus bias (filled only with SFFN_FLAG_KEEP_DENSE) */
     size_t y2_vals, y2_meta, colidx;/* V:N:M y2: [T, F/4] bf16, [T, F/16] u8, [T/64, F/8, 4] u8 */
-    size_t dy2;                     /* [T, F] bf16, eq. (4) */
+    size_t dy2;                     /* [T, F] bf16, eq. (4) (filled only with SFFN_FLAG_KEEP_DENSE) */
     size_t dy1_vals;                /* [T, F/4] bf16, eq. (6) in y2's slots */
+    size_t y1_kept;                 /* [T, F/4] bf16, y1 at y2's kept slots: what Alg. 2 line 1 needs of y1 */
     size_t total;                   /* bytes needed */
 } sffn_ws_layout;
 

@@ -19,12 +19,12 @@ class SffnError(RuntimeError):
 
 class _Cfg(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int64), ("D", ctypes.c_int64), ("F", ctypes.c_int64), ("V", ctypes.c_int32),
-                ("M", ctypes.c_int32), ("mode", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("M", ctypes.c_int32), ("mode", ctypes.c_int32), ("flags", ctypes.c_int32)]
 
 
 class _Layout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta", "y1", "y2_vals", "y2_meta",
-                                               "colidx", "dy2", "dy1_vals", "total")]
+                                               "colidx", "dy2", "dy1_vals", "y1_kept", "total")]
 
 
 def lib_path():
@@ -113,8 +113,11 @@ def profile_read():
     return [(names[i].decode(), float(ms[i])) for i in range(n)]
 
 
-def _cfg(T, D, F, mode=MODE_HARD, V=64, M=8):
-    return _Cfg(T, D, F, V, M, mode, 0)
+FLAG_KEEP_DENSE = 1
+
+
+def _cfg(T, D, F, mode=MODE_HARD, V=64, M=8, flags=0):
+    return _Cfg(T, D, F, V, M, mode, flags)
 
 
 def workspace_bytes(T, D, F, mode=MODE_HARD):
@@ -194,9 +197,11 @@ def vnm_wgrad(a_vals, a_meta, a_colidx, G, out_f_major, V=64, M=8):
 class FfnStep:
     """Pre-allocated outputs and workspace for repeated ffn_sparse_step calls on one shape."""
 
-    def __init__(self, T, D, F, mode=MODE_HARD, device="cuda"):
-        self.T, self.D, self.F, self.mode = T, D, F, mode
-        self.cfg = _cfg(T, D, F, mode)
+    def __init__(self, T, D, F, mode=MODE_HARD, device="cuda", keep_dense=False):
+        """keep_dense: also store the dense y1 and dy2 (SFFN_FLAG_KEEP_DENSE); otherwise only y1 at y2's kept
+        slots is saved for the backward pass."""
+        self.T, self.D, self.F, self.mode, self.keep_dense = T, D, F, mode, keep_dense
+        self.cfg = _cfg(T, D, F, mode, flags=FLAG_KEEP_DENSE if keep_dense else 0)
         self.layout = workspace_layout(T, D, F, mode)
         self.ws = _u8((self.layout["total"],), device)
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
@@ -222,12 +227,13 @@ class FfnStep:
                     w2t_vals=view(L["w2t_vals"], (F, D // 2), torch.bfloat16), w2t_meta=view(L["w2t_meta"], (F, D // 8), torch.uint8),
                     y1=view(L["y1"], (T, F), torch.bfloat16), y2_vals=view(L["y2_vals"], (T, F // 4), torch.bfloat16),
                     y2_meta=view(L["y2_meta"], (T, F // 16), torch.uint8), colidx=view(L["colidx"], (T // 64, F // 8, 4), torch.uint8),
-                    dy2=view(L["dy2"], (T, F), torch.bfloat16), dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16))
+                    dy2=view(L["dy2"], (T, F), torch.bfloat16), dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16),
+                    y1_kept=view(L["y1_kept"], (T, F // 4), torch.bfloat16))
 
 
-def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD):
+def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD, keep_dense=True):
     T, D = X.shape
     F = W1.shape[0]
-    step = FfnStep(T, D, F, mode, X.device)
+    step = FfnStep(T, D, F, mode, X.device, keep_dense)
     out = step(X, W1, W2, b1, dY)
     return out, step

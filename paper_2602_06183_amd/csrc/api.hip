@@ -56,6 +56,7 @@ bool make_layout(const sffn_cfg* c, FullLayout* L) {
     L->pub.y2_vals = take(T * F / 2);      L->pub.y2_meta = take(T * F / 16);   L->pub.colidx = take(T / 64 * (F / 8) * 4);
     L->pub.dy2 = take(T * F * 2);
     L->pub.dy1_vals = take(T * F / 2);
+    L->pub.y1_kept = take(T * F / 2);
     L->w1_vblk = take(F * D);              L->w1_mblk = take(F * D / 8);
     L->w2t_vblk = take(F * D);             L->w2t_mblk = take(F * D / 8);
     L->x_blk = take(T * D * 2);            L->xt_blk = take(D * T * 2);
@@ -238,27 +239,35 @@ int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, 
     uint16_t* w2b = (uint16_t*)(ws + L.w2_blk);         uint16_t* w1tb = (uint16_t*)(ws + L.w1t_blk);
     uint16_t* a24v = (uint16_t*)(ws + L.a24_vblk);      uint8_t* a24m = ws + L.a24_mblk;
     uint16_t* atb = (uint16_t*)(ws + L.at_blk);
+    uint16_t* ykept = (uint16_t*)(ws + L.pub.y1_kept);
+    const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
 
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
     // Every GEMM operand is first brought into the blocked layout by the kernel that reads or produces it
     // anyway: X, dY and W1 by the transposes the weight-gradient / input-gradient GEMMs need, W2 by its
-    // pruning pass, the activations by the compressors.
+    // pruning pass, the activations by the fused epilogues of eqs. (1) and (4).
     // ---- Alg. 1 -------------------------------------------------------------------------------
     STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
     STAGE(launch_prune24_step(W1, F, D, D, 0, cfg->mode, w1v, w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
-    STAGE(launch_gemm_nt_blocked(1, w1vb, w1mb, xb, b1, F, T, D, 1, y1, F, s), "step/y1");                  // eq. (1)
-    STAGE(launch_sqrelu_vnm_compress(y1, T, F, y2v, y2m, cix, a24v, a24m, s), "step/sqrelu_vnm_compress");  // eq. (2) + V:N:M
+    {   // eq. (1), then eq. (2) + V:N:M compression on the tile while it is still in LDS
+        VnmEpilogue ep;
+        ep.mode = 1; ep.store_dense = keep_dense; ep.vals = y2v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
+        ep.v24 = a24v; ep.m24 = a24m; ep.at = atb;
+        STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s), "step/y1+sqrelu_vnm_compress");
+    }
     STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, w2v, w2m, w2vb, w2mb, w2b, s), "step/prune24(W2.T)");
     STAGE(launch_gemm_nt_blocked(1, a24v, a24m, w2b, nullptr, T, D, F, 0, Y3, D, s), "step/y3");            // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
     STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
-    STAGE(launch_gemm_nt_blocked(1, w2vb, w2mb, dyb, nullptr, F, T, D, 1, dy2, F, s), "step/dy2");          // eq. (4)
-    STAGE(launch_vnm_expand_t(y2v, y2m, cix, T, F, atb, 1, s), "step/y2 expand");
     STAGE(launch_gemm_nt_blocked(0, atb, nullptr, dytb, nullptr, F, D, T, 1, dW2, F, s), "step/dW2");       // eq. (5)
-    STAGE(launch_dsqrelu_vnm(dy2, y1, y2m, cix, T, F, dy1v, a24v, a24m, s), "step/dsqrelu_vnm");            // eq. (6)
+    {   // eq. (4), then eq. (6) on y2's kept slots; overwrites the 2:4 view and the transposed tile with dy1's
+        VnmEpilogue ep;
+        ep.mode = 2; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
+        ep.v24 = a24v; ep.m24 = a24m; ep.at = atb;
+        STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, ep, s), "step/dy2+dsqrelu_vnm");
+    }
     STAGE(launch_transpose(W1, F, D, D, w1tb, 1, nullptr, s), "step/W1.T");
     STAGE(launch_gemm_nt_blocked(1, a24v, a24m, w1tb, nullptr, T, D, F, 0, dX, D, s), "step/dX");           // eq. (7)
-    STAGE(launch_vnm_expand_t(dy1v, y2m, cix, T, F, atb, 1, s), "step/dy1 expand");
     STAGE(launch_gemm_nt_blocked(0, atb, nullptr, xtb, nullptr, F, D, T, 0, dW1, D, s), "step/dW1");        // eq. (8)
     return SFFN_OK;
 }

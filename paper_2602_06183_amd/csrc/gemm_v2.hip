@@ -56,11 +56,17 @@ struct Cfg {
 
 }  // namespace
 
-template <bool SPARSE, bool OUT_I_CONTIG>
+__device__ __forceinline__ uint32_t sqrelu16(uint32_t y) {          // bf16 bits -> bf16 bits of max(y, 0)^2
+    const float f = bf2f(y), r = f > 0.0f ? f : 0.0f;
+    return f2bf(r * r);
+}
+
+template <bool SPARSE, bool OUT_I_CONTIG, int EPI>
 __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restrict__ a_vals, const uint8_t* __restrict__ a_meta,
                                                         const uint16_t* __restrict__ B, const float* __restrict__ bias,
                                                         int Ra, int Rb, int K, uint16_t* __restrict__ out, int64_t ldo,
-                                                        int tiles_m, int tiles_n, int blocked) {
+                                                        int tiles_m, int tiles_n, int blocked, VnmEpilogue ep) {
+    static_assert(EPI == 0 || (SPARSE && OUT_I_CONTIG), "the V:N:M epilogues belong to the 2:4-weight GEMMs");
     using C = Cfg<SPARSE>;
     constexpr int BM = C::BM, BN = C::BN, WM = 128, WN = 64, FM = 4, FN = 2;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[C::NSTAGE * C::STAGE];
@@ -244,10 +250,19 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         // through LDS as [j][i] (two halves of 64 i) so that HBM sees 128-byte row segments instead of
         // 16-byte ones; the bias (indexed by i) is added before the single rounding to bf16.
         constexpr int EP = 64 * 2 + 16;
-        unsigned char* scratch = smem + wave * (WN * EP);
-        static_assert(8 * WN * EP <= C::NSTAGE * C::STAGE, "epilogue scratch must fit in the main-loop LDS");
+        constexpr int WAVE_LDS = (EPI != 0) ? 2 * WN * EP : WN * EP;     // EPI: second tile for the transposed output
+        unsigned char* scratch = smem + wave * WAVE_LDS;
+        static_assert(8 * WAVE_LDS <= C::NSTAGE * C::STAGE, "epilogue scratch must fit in the main-loop LDS");
+        unsigned char* ttile = scratch + WN * EP;
+        // EPI: i = hidden unit f, j = token t; the wave's 64 tokens are exactly one V = 64 block and each half of
+        // 64 f holds 8 whole column blocks, so the V:N:M work is wave-local.
+        const int t0 = j0 + wn * WN;
+        const int nblk = Ra >> 3;
+        const int64_t F = Ra;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
+            const int f0 = i0 + wm * WM + h * 64;
+            const bool valid = t0 < Rb && f0 < Ra;
 #pragma unroll
             for (int a2 = 0; a2 < 2; ++a2)
 #pragma unroll
@@ -258,20 +273,112 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         const int il = a2 * 32 + 8 * g + 4 * lh;              // i inside the 64-wide half
                         float v0 = acc[a][b][4 * g], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2], v3 = acc[a][b][4 * g + 3];
                         if (bias) {
-                            int i = i0 + wm * WM + h * 64 + il; i = i < Ra ? i : Ra - 4;
+                            int i = f0 + il; i = i < Ra ? i : Ra - 4;
                             const float4 bb = *reinterpret_cast<const float4*>(bias + i);
                             v0 += bb.x; v1 += bb.y; v2 += bb.z; v3 += bb.w;
                         }
                         *reinterpret_cast<uint2*>(scratch + (b * 32 + l32) * EP + il * 2) =
                             make_uint2(f2bf(v0) | (f2bf(v1) << 16), f2bf(v2) | (f2bf(v3) << 16));
                     }
-            __syncthreads();
+            if (EPI != 0) {
 #pragma unroll
-            for (int p = 0; p < WN / 8; ++p) {
-                const int row = p * 8 + (lane >> 3), ch = lane & 7;
-                const int j = j0 + wn * WN + row, i = i0 + wm * WM + h * 64 + ch * 8;
-                if (j < Rb && i < Ra)
-                    *reinterpret_cast<uint4*>(out + (int64_t)j * ldo + i) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
+                for (int q = 0; q < WN * EP / 1024; ++q) *reinterpret_cast<uint4*>(ttile + (q * 64 + lane) * 16) = make_uint4(0, 0, 0, 0);
+            }
+            __syncthreads();
+            if (EPI == 0 || ep.store_dense) {
+#pragma unroll
+                for (int p = 0; p < WN / 8; ++p) {
+                    const int row = p * 8 + (lane >> 3), ch = lane & 7;
+                    const int j = t0 + row, i = f0 + ch * 8;
+                    if (j < Rb && i < Ra)
+                        *reinterpret_cast<uint4*>(out + (int64_t)j * ldo + i) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
+                }
+            }
+            if (EPI != 0) {
+                const int bl = lane & 7;                                  // column block handled in the per-row pass
+                const int64_t blk_g = (f0 >> 3) + bl;
+                uint32_t cw;                                              // the four kept column offsets of block bl
+                if (EPI == 1) {
+                    // column scores: lane = column, strict ascending-row fp32 sum of y2 = bf16(max(y1, 0)^2)
+                    float sc = 0.0f;
+#pragma unroll 8
+                    for (int r = 0; r < WN; ++r)
+                        sc = sc + bf2f(sqrelu16(*reinterpret_cast<const uint16_t*>(scratch + r * EP + lane * 2)));
+                    int rank = 0;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const float o = __shfl(sc, (lane & ~7) + k, 64);
+                        rank += (k < bl) ? (o >= sc) : ((k > bl) ? (o > sc) : 0);
+                    }
+                    const unsigned long long kept = __ballot(rank < 4);
+                    const uint32_t bits = (uint32_t)(kept >> (lane & ~7)) & 0xFFu;
+                    uint32_t mine = 0, n = 0;
+#pragma unroll
+                    for (int c = 0; c < 8; ++c)
+                        if ((bits >> c) & 1u) { mine |= (uint32_t)c << (8 * n); ++n; }
+                    if (valid && bl == 0)
+                        *reinterpret_cast<uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblk + (f0 >> 3) + (lane >> 3)) * 4) = mine;
+                    cw = (uint32_t)__shfl((int)mine, bl * 8, 64);
+                } else {
+                    cw = valid ? *reinterpret_cast<const uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblk + blk_g) * 4) : 0x03020100u;
+                }
+#pragma unroll
+                for (int it = 0; it < 8; ++it) {
+                    const int t = (lane >> 3) + 8 * it;
+                    const int64_t tg = t0 + t;
+                    const unsigned char* row = scratch + t * EP + bl * 16;
+                    uint32_t v, nib;
+                    if (EPI == 1) {
+                        const uint32_t y0 = *reinterpret_cast<const uint16_t*>(row + (cw & 0xFFu) * 2);
+                        const uint32_t y1 = *reinterpret_cast<const uint16_t*>(row + ((cw >> 8) & 0xFFu) * 2);
+                        const uint32_t y2 = *reinterpret_cast<const uint16_t*>(row + ((cw >> 16) & 0xFFu) * 2);
+                        const uint32_t y3 = *reinterpret_cast<const uint16_t*>(row + (cw >> 24) * 2);
+                        v = select24<false>(sqrelu16(y0), sqrelu16(y1), sqrelu16(y2), sqrelu16(y3), nib);
+                        const uint32_t p0 = nib & 3u, p1 = nib >> 2;
+                        const uint32_t k0 = (p0 == 0) ? y0 : (p0 == 1) ? y1 : y2;
+                        const uint32_t k1 = (p1 == 3) ? y3 : (p1 == 2) ? y2 : y1;
+                        const uint32_t other = (uint32_t)__shfl_xor((int)nib, 1, 64);
+                        if (valid) {
+                            *reinterpret_cast<uint32_t*>(ep.vals + tg * (F / 4) + blk_g * 2) = v;
+                            *reinterpret_cast<uint32_t*>(ep.ykept + tg * (F / 4) + blk_g * 2) = k0 | (k1 << 16);
+                            if ((lane & 1) == 0) ep.meta[tg * (F / 16) + (blk_g >> 1)] = (uint8_t)(nib | (other << 4));
+                        }
+                    } else {
+                        uint32_t mb = 0x44u, yk = 0u;
+                        if (valid) {
+                            mb = ep.meta[tg * (F / 16) + (blk_g >> 1)];
+                            yk = *reinterpret_cast<const uint32_t*>(ep.ykept + tg * (F / 4) + blk_g * 2);
+                        }
+                        nib = (mb >> (4 * (bl & 1))) & 0xFu;
+                        const uint32_t o0 = (cw >> (8 * (nib & 3u))) & 0xFFu, o1 = (cw >> (8 * (nib >> 2))) & 0xFFu;
+                        const float d0 = bf2f(*reinterpret_cast<const uint16_t*>(row + o0 * 2));
+                        const float d1 = bf2f(*reinterpret_cast<const uint16_t*>(row + o1 * 2));
+                        const float ya = bf2f(yk & 0xFFFFu), yb = bf2f(yk >> 16);
+                        const float ga = 2.0f * d0 * (ya > 0.0f ? ya : 0.0f), gb = 2.0f * d1 * (yb > 0.0f ? yb : 0.0f);
+                        v = f2bf(ga) | (f2bf(gb) << 16);
+                        if (valid) *reinterpret_cast<uint32_t*>(ep.vals + tg * (F / 4) + blk_g * 2) = v;
+                    }
+                    // the same block as two plain 2:4 groups (blocked operand of eq. (3) / eq. (7))
+                    uint32_t a24, b24, mb8;
+                    vnm_block_to_24(v, nib, cw, a24, b24, mb8);
+                    uint32_t m4 = mb8 | ((uint32_t)__shfl_down((int)mb8, 1, 64) << 8);
+                    m4 |= (uint32_t)__shfl_down((int)m4, 2, 64) << 16;
+                    if (valid) {
+                        *reinterpret_cast<uint2*>(ep.v24 + blk_off(tg, blk_g * 4, F / 64)) = make_uint2(a24, b24);
+                        if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(ep.m24 + mblk_off(tg, blk_g * 8, F / 64)) = m4;
+                    }
+                    // dense transposed tile for the weight-gradient GEMM: row = hidden unit, column = token
+                    const uint32_t o0 = (cw >> (8 * (nib & 3u))) & 0xFFu, o1 = (cw >> (8 * (nib >> 2))) & 0xFFu;
+                    *reinterpret_cast<uint16_t*>(ttile + (bl * 8 + o0) * EP + t * 2) = (uint16_t)(v & 0xFFFFu);
+                    *reinterpret_cast<uint16_t*>(ttile + (bl * 8 + o1) * EP + t * 2) = (uint16_t)(v >> 16);
+                }
+                __syncthreads();
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {          // 4 groups of 16 hidden units x 2 chunks of 32 tokens, 1 KB each
+                    const int fr = (q >> 1) * 16 + (lane >> 2), tc = (q & 1) * 32 + (lane & 3) * 8;
+                    if (valid)
+                        *reinterpret_cast<uint4*>(ep.at + blk_off(f0 + fr, t0 + tc, Rb / 32)) = *reinterpret_cast<const uint4*>(ttile + fr * EP + tc * 2);
+                }
             }
             __syncthreads();
         }
@@ -306,12 +413,13 @@ static hipError_t launch_v2(const uint16_t* a_vals, const uint8_t* a_meta, const
                             int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, int blocked, hipStream_t s) {
     const int tiles_m = (int)((Ra + 255) / 256), tiles_n = (int)((Rb + 255) / 256);
     dim3 grid((unsigned)(tiles_m * tiles_n));
+    const VnmEpilogue none;
     if (out_i_contig)
-        hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
-                           out, ldo, tiles_m, tiles_n, blocked);
+        hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, true, 0>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
+                           out, ldo, tiles_m, tiles_n, blocked, none);
     else
-        hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, false>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
-                           out, ldo, tiles_m, tiles_n, blocked);
+        hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, false, 0>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
+                           out, ldo, tiles_m, tiles_n, blocked, none);
     return hipGetLastError();
 }
 
@@ -325,6 +433,19 @@ hipError_t launch_gemm_nt_blocked(int sparse_a, const uint16_t* a_vals, const ui
                                   int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
     if (sparse_a) return launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 1, s);
     return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 1, s);
+}
+
+hipError_t launch_gemm_vnm_epilogue(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t F,
+                                    int64_t T, int64_t K, uint16_t* out, const VnmEpilogue& ep, hipStream_t s) {
+    const int tiles_m = (int)((F + 255) / 256), tiles_n = (int)((T + 255) / 256);
+    dim3 grid((unsigned)(tiles_m * tiles_n));
+    if (ep.mode == 1)
+        hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 1>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
+                           tiles_m, tiles_n, 1, ep);
+    else
+        hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 2>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
+                           tiles_m, tiles_n, 1, ep);
+    return hipGetLastError();
 }
 
 }  // namespace sffn

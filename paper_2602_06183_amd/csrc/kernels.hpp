@@ -5,6 +5,25 @@
 
 namespace sffn {
 
+// Fused V:N:M epilogue of the two GEMMs whose output feeds the activation sparsifier (ffn_sparse_step only).
+//   mode 1 (eq. (1) -> eq. (2) + Section 2.3): the tile of y1 is squared-ReLU'd and compressed in place: outputs the
+//          canonical V:N:M y2 (vals, meta, colidx), y1 at the kept slots (ykept, same indexing as vals), the plain
+//          2:4 view (v24, m24; blocked layout) and the dense transposed y2v (at; blocked layout, rows = F).
+//   mode 2 (eq. (4) -> eq. (6)): the tile of dy2 meets (meta, colidx, ykept) and becomes dy1 in y2's slots: outputs
+//          vals (= dy1 values), v24 / m24 and at as above.
+//   store_dense: also write the dense GEMM output (y1 / dy2) to `out`.
+struct VnmEpilogue {
+    int mode = 0;
+    int store_dense = 1;
+    uint16_t* vals = nullptr;
+    uint8_t* meta = nullptr;
+    uint8_t* colidx = nullptr;
+    uint16_t* ykept = nullptr;
+    uint16_t* v24 = nullptr;
+    uint8_t* m24 = nullptr;
+    uint16_t* at = nullptr;
+};
+
 hipError_t launch_prune24(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
                           uint8_t* meta, hipStream_t stream);
 // v24blk / m24blk (both or neither): also write the result as a plain 2:4 matrix over all F columns in the
@@ -29,6 +48,9 @@ hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld
 //             structured-sparse matrix cores; else a_vals is a dense [Ra, K] matrix.
 //   out_i_contig: 1 -> out[j * ldo + i] (+ bias[i]);  0 -> out[i * ldo + j].
 //   blocked (launch_gemm_nt_blocked): both operands (and the metadata) are in the blocked layout of common.hpp.
+// eq. (1) / eq. (4) with the fused epilogue above: A packed 2:4 [Ra = F rows], B = [Rb = T rows], all blocked; out [T, F].
+hipError_t launch_gemm_vnm_epilogue(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t F,
+                                    int64_t T, int64_t K, uint16_t* out, const VnmEpilogue& ep, hipStream_t s);
 hipError_t launch_gemm_nt_blocked(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
                                   int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
 hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,

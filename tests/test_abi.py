@@ -33,7 +33,7 @@ def test_workspace_queries():
     assert sffn.workspace_bytes(512, 256, 1024) > 0
     assert sffn.workspace_bytes(500, 256, 1024) == 0          # T not a multiple of 64
     lay = sffn.workspace_layout(512, 256, 1024)
-    offs = [lay[k] for k in ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta", "y1", "y2_vals", "y2_meta", "colidx", "dy2", "dy1_vals")]
+    offs = [lay[k] for k in ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta", "y1", "y2_vals", "y2_meta", "colidx", "dy2", "dy1_vals", "y1_kept")]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs) and lay["total"] == sffn.workspace_bytes(512, 256, 1024)
     lib = sffn.load()
     assert lib.sffn_vnm_spmm_workspace_bytes(64, 64, 64, 1) > lib.sffn_vnm_spmm_workspace_bytes(64, 64, 64, 0) > 0

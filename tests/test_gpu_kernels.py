@@ -165,6 +165,14 @@ def _teacher_forced_step_check(T, D, F, mode, seed):
     assert_gemm_close(s["y1"], oracle.spmm24(inp["X"], s["w1_vals"], s["w1_meta"], inp["b1"]), "y1")
     yv, ym, yc = oracle.sqrelu_vnm_compress(s["y1"])
     assert np.array_equal(s["colidx"], yc) and np.array_equal(s["y2_meta"], ym) and np.array_equal(s["y2_vals"], yv)
+    # y1 at the kept slots: gather from the GPU's dense y1 with the oracle's own metadata
+    ones = np.arange(1, yv.size + 1, dtype=np.uint32).reshape(yv.shape)
+    slot_of = oracle.vnm_decompress((ones & 0xFFFF).astype(np.uint16), ym, yc).astype(np.int64) \
+        + (oracle.vnm_decompress((ones >> 16).astype(np.uint16), ym, yc).astype(np.int64) << 16)
+    want_kept = np.zeros(yv.size, dtype=np.uint16)
+    tt, ff = np.nonzero(slot_of)
+    want_kept[slot_of[tt, ff] - 1] = s["y1"][tt, ff]
+    assert np.array_equal(s["y1_kept"].reshape(-1), want_kept)
     assert_gemm_close(to_bits(Y3), oracle.vnm_spmm(yv, ym, yc, inp["W2"], 0), "y3")
     rv2, rm2 = oracle.prune24_compress(np.ascontiguousarray(inp["W2"].T), mode)
     assert np.array_equal(s["w2t_vals"], rv2) and np.array_equal(s["w2t_meta"], rm2)
@@ -196,6 +204,22 @@ def test_ffn_sparse_step_tiny_config(mode):
 
 def test_ffn_sparse_step_ragged_shape():
     _teacher_forced_step_check(192, 320, 448, sffn.MODE_SOFT, seed=3)
+
+
+def test_step_without_dense_intermediates_is_bit_identical():
+    """The benchmarked configuration does not store the dense y1 / dy2; everything else it produces must be the
+    same bits as the checked configuration that does."""
+    inp = make_ffn_inputs(512, 256, 1024, seed=0)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    res = []
+    for keep in (True, False):
+        step = sffn.FfnStep(512, 256, 1024, sffn.MODE_SOFT, keep_dense=keep)
+        outs = [to_bits(t).copy() for t in step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+        sv = step.saved()
+        outs += [to_bits(sv[k]).copy() for k in ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta", "y2_vals", "y2_meta", "colidx", "dy1_vals", "y1_kept")]
+        res.append(outs)
+    for a, b in zip(*res):
+        assert np.array_equal(a, b)
 
 
 def test_step_is_deterministic_and_reusable():
