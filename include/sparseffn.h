@@ -73,7 +73,8 @@ typedef struct sffn_ws_layout {
     size_t y2_vals, y2_meta, colidx;/* V:N:M y2: [T, F/4] bf16, [T, F/16] u8, [T/64, F/8, 4] u8 */
     size_t dy2;                     /* [T, F] bf16, eq. (4) (filled only with SFFN_FLAG_KEEP_DENSE) */
     size_t dy1_vals;                /* [T, F/4] bf16, eq. (6) in y2's slots */
-    size_t y1_kept;                 /* [T, F/4] bf16, y1 at y2's kept slots: what Alg. 2 line 1 needs of y1 */
+    size_t y1_kept;                 /* T*F/4 bf16, y1 at y2's kept slots (what Alg. 2 line 1 needs of y1), stored as
+                                     * [T/64][F/64][64 tokens][8 column blocks][2] */
     size_t total;                   /* bytes needed */
 } sffn_ws_layout;
 

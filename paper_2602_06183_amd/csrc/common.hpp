@@ -64,17 +64,29 @@ __host__ __device__ __forceinline__ int64_t mblk_off(int64_t r, int64_t k, int64
 __device__ __forceinline__ void vnm_block_to_24(uint32_t v, uint32_t nib, uint32_t cw, uint32_t& a, uint32_t& b, uint32_t& mbyte) {
     const uint32_t o0 = (cw >> (8 * (nib & 3u))) & 0xFFu, o1 = (cw >> (8 * (nib >> 2))) & 0xFFu;   // o0 < o1
     const uint32_t v0 = v & 0xFFFFu, v1 = v >> 16;
-    uint32_t na, nb;
-    if (o1 < 4) {
-        a = v; na = o0 | (o1 << 2); b = 0; nb = 0x4;
-    } else if (o0 >= 4) {
-        a = 0; na = 0x4; b = v; nb = (o0 - 4) | ((o1 - 4) << 2);
-    } else {
-        if (o0 < 3) { a = v0; na = o0 | (3u << 2); } else { a = v0 << 16; na = 0u | (3u << 2); }
-        const uint32_t q = o1 - 4;
-        if (q > 0) { b = v1 << 16; nb = 0u | (q << 2); } else { b = v1; nb = 0u | (1u << 2); }
-    }
+    const bool lo0 = o0 < 4, lo1 = o1 < 4;            // survivor in columns 0-3?  (lo1 implies lo0)
+    // low group: both survivors | only the first (kept next to an empty slot at position 3, or after one at 0) | none
+    const uint32_t a_split = (o0 < 3) ? v0 : (v0 << 16), na_split = (o0 < 3) ? (o0 | (3u << 2)) : (3u << 2);
+    a = lo1 ? v : (lo0 ? a_split : 0u);
+    const uint32_t na = lo1 ? (o0 | (o1 << 2)) : (lo0 ? na_split : 0x4u);
+    // high group: both | only the second | none
+    const uint32_t q = o1 - 4;
+    const uint32_t b_split = (q > 0) ? (v1 << 16) : v1, nb_split = (q > 0) ? (q << 2) : 0x4u;
+    b = !lo0 ? v : (!lo1 ? b_split : 0u);
+    const uint32_t nb = !lo0 ? ((o0 - 4) | (q << 2)) : (!lo1 ? nb_split : 0x4u);
     mbyte = na | (nb << 4);
+}
+
+// lane i <- lane i + N inside a row of 16 lanes (0 past the row's end): one DPP move instead of an LDS permute
+template <int N>
+__device__ __forceinline__ uint32_t row_shl(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x100 | N, 0xF, 0xF, true);
+}
+
+// y1 at y2's kept slots, as the fused epilogues write and read it: 2 KB runs of (64 tokens x 8 column blocks);
+// index in 32-bit words of (token t, column block blk), F = d_ffn.
+__host__ __device__ __forceinline__ int64_t ykept_off(int64_t t, int64_t blk, int64_t F) {
+    return ((((t >> 6) * (F >> 6) + (blk >> 3)) << 6) + (t & 63)) * 8 + (blk & 7);
 }
 
 }  // namespace sffn

@@ -56,9 +56,20 @@ struct Cfg {
 
 }  // namespace
 
-__device__ __forceinline__ uint32_t sqrelu16(uint32_t y) {          // bf16 bits -> bf16 bits of max(y, 0)^2
+// bf16 bits -> max(y, 0)^2 rounded to bf16 (RNE), returned as the fp32 bit pattern (low half zero).
+// r * r is never NaN here (a NaN input fails the comparison and becomes 0), so no NaN path is needed.
+__device__ __forceinline__ uint32_t sqrelu_hi(uint32_t y) {
     const float f = bf2f(y), r = f > 0.0f ? f : 0.0f;
-    return f2bf(r * r);
+    const uint32_t u = __float_as_uint(r * r);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;
+}
+__device__ __forceinline__ uint32_t sqrelu16(uint32_t y) { return sqrelu_hi(y) >> 16; }
+// ordering point between LDS writes and reads of lanes of the same wavefront (its LDS operations execute in
+// issue order; this only stops the compiler from moving them)
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 template <bool SPARSE, bool OUT_I_CONTIG, int EPI>
@@ -284,7 +295,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
 #pragma unroll
                 for (int q = 0; q < WN * EP / 1024; ++q) *reinterpret_cast<uint4*>(ttile + (q * 64 + lane) * 16) = make_uint4(0, 0, 0, 0);
             }
-            __syncthreads();
+            wave_lds_sync();
             if (EPI == 0 || ep.store_dense) {
 #pragma unroll
                 for (int p = 0; p < WN / 8; ++p) {
@@ -303,7 +314,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                     float sc = 0.0f;
 #pragma unroll 8
                     for (int r = 0; r < WN; ++r)
-                        sc = sc + bf2f(sqrelu16(*reinterpret_cast<const uint16_t*>(scratch + r * EP + lane * 2)));
+                        sc = sc + __uint_as_float(sqrelu_hi(*reinterpret_cast<const uint16_t*>(scratch + r * EP + lane * 2)));
                     int rank = 0;
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
@@ -322,57 +333,61 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                 } else {
                     cw = valid ? *reinterpret_cast<const uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblk + blk_g) * 4) : 0x03020100u;
                 }
+                // per-row pass: lane = (column block bl, token t); 8 tokens per sweep, 8 sweeps
+                uint32_t* vals_p = reinterpret_cast<uint32_t*>(ep.vals) + ((int64_t)(t0 + (lane >> 3)) * (F / 4) + blk_g * 2) / 2;
+                uint32_t* kept_p = reinterpret_cast<uint32_t*>(ep.ykept) + ykept_off(t0 + (lane >> 3), blk_g, F);
+                uint8_t* meta_p = ep.meta + (int64_t)(t0 + (lane >> 3)) * (F / 16) + (blk_g >> 1);
+                uint16_t* v24_p = ep.v24 + blk_off(t0 + (lane >> 3), blk_g * 4, F / 64);
+                uint8_t* m24_p = ep.m24 + mblk_off(t0 + (lane >> 3), blk_g * 8, F / 64);
+                const uint32_t c0 = (cw & 0xFFu) * 2, c1 = ((cw >> 8) & 0xFFu) * 2, c2 = ((cw >> 16) & 0xFFu) * 2, c3 = (cw >> 24) * 2;
+                if (valid) {
 #pragma unroll
-                for (int it = 0; it < 8; ++it) {
-                    const int t = (lane >> 3) + 8 * it;
-                    const int64_t tg = t0 + t;
-                    const unsigned char* row = scratch + t * EP + bl * 16;
-                    uint32_t v, nib;
-                    if (EPI == 1) {
-                        const uint32_t y0 = *reinterpret_cast<const uint16_t*>(row + (cw & 0xFFu) * 2);
-                        const uint32_t y1 = *reinterpret_cast<const uint16_t*>(row + ((cw >> 8) & 0xFFu) * 2);
-                        const uint32_t y2 = *reinterpret_cast<const uint16_t*>(row + ((cw >> 16) & 0xFFu) * 2);
-                        const uint32_t y3 = *reinterpret_cast<const uint16_t*>(row + (cw >> 24) * 2);
-                        v = select24<false>(sqrelu16(y0), sqrelu16(y1), sqrelu16(y2), sqrelu16(y3), nib);
-                        const uint32_t p0 = nib & 3u, p1 = nib >> 2;
-                        const uint32_t k0 = (p0 == 0) ? y0 : (p0 == 1) ? y1 : y2;
-                        const uint32_t k1 = (p1 == 3) ? y3 : (p1 == 2) ? y2 : y1;
-                        const uint32_t other = (uint32_t)__shfl_xor((int)nib, 1, 64);
-                        if (valid) {
-                            *reinterpret_cast<uint32_t*>(ep.vals + tg * (F / 4) + blk_g * 2) = v;
-                            *reinterpret_cast<uint32_t*>(ep.ykept + tg * (F / 4) + blk_g * 2) = k0 | (k1 << 16);
-                            if ((lane & 1) == 0) ep.meta[tg * (F / 16) + (blk_g >> 1)] = (uint8_t)(nib | (other << 4));
+                    for (int it = 0; it < 8; ++it) {
+                        const int t = (lane >> 3) + 8 * it;
+                        const unsigned char* row = scratch + t * EP + bl * 16;
+                        uint32_t v, nib;
+                        if (EPI == 1) {
+                            const uint32_t y0 = *reinterpret_cast<const uint16_t*>(row + c0);
+                            const uint32_t y1 = *reinterpret_cast<const uint16_t*>(row + c1);
+                            const uint32_t y2 = *reinterpret_cast<const uint16_t*>(row + c2);
+                            const uint32_t y3 = *reinterpret_cast<const uint16_t*>(row + c3);
+                            v = select24<false>(sqrelu16(y0), sqrelu16(y1), sqrelu16(y2), sqrelu16(y3), nib);
+                            const uint32_t p0 = nib & 3u, p1 = nib >> 2;
+                            const uint32_t k0 = (p0 == 0) ? y0 : (p0 == 1) ? y1 : y2;
+                            const uint32_t k1 = (p1 == 3) ? y3 : (p1 == 2) ? y2 : y1;
+                            vals_p[(int64_t)it * 8 * (F / 8)] = v;
+                            kept_p[it * 64] = k0 | (k1 << 16);
+                            // metadata bytes of the row's 8 blocks -> one 32-bit store from the lane of block 0
+                            uint32_t mw = nib | (row_shl<1>(nib) << 4);
+                            mw |= row_shl<2>(mw) << 8;
+                            mw |= row_shl<4>(mw) << 16;
+                            if (bl == 0) *reinterpret_cast<uint32_t*>(meta_p + (int64_t)it * 8 * (F / 16)) = mw;
+                        } else {
+                            const uint32_t mb = meta_p[(int64_t)it * 8 * (F / 16)];
+                            const uint32_t yk = kept_p[it * 64];
+                            nib = (mb >> (4 * (bl & 1))) & 0xFu;
+                            const uint32_t q0 = (cw >> (8 * (nib & 3u))) & 0xFFu, q1 = (cw >> (8 * (nib >> 2))) & 0xFFu;
+                            const float d0 = bf2f(*reinterpret_cast<const uint16_t*>(row + q0 * 2));
+                            const float d1 = bf2f(*reinterpret_cast<const uint16_t*>(row + q1 * 2));
+                            const float ya = bf2f(yk & 0xFFFFu), yb = bf2f(yk >> 16);
+                            const float ga = 2.0f * d0 * (ya > 0.0f ? ya : 0.0f), gb = 2.0f * d1 * (yb > 0.0f ? yb : 0.0f);
+                            v = f2bf(ga) | (f2bf(gb) << 16);
+                            vals_p[(int64_t)it * 8 * (F / 8)] = v;
                         }
-                    } else {
-                        uint32_t mb = 0x44u, yk = 0u;
-                        if (valid) {
-                            mb = ep.meta[tg * (F / 16) + (blk_g >> 1)];
-                            yk = *reinterpret_cast<const uint32_t*>(ep.ykept + tg * (F / 4) + blk_g * 2);
-                        }
-                        nib = (mb >> (4 * (bl & 1))) & 0xFu;
+                        // the same block as two plain 2:4 groups (blocked operand of eq. (3) / eq. (7))
+                        uint32_t a24, b24, mb8;
+                        vnm_block_to_24(v, nib, cw, a24, b24, mb8);
+                        uint32_t m4 = mb8 | (row_shl<1>(mb8) << 8);
+                        m4 |= row_shl<2>(m4) << 16;
+                        *reinterpret_cast<uint2*>(v24_p + (int64_t)(it >> 1) * (F / 64) * 512 + (it & 1) * 256) = make_uint2(a24, b24);
+                        if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(m24_p + it * 64) = m4;
+                        // dense transposed tile for the weight-gradient GEMM: row = hidden unit, column = token
                         const uint32_t o0 = (cw >> (8 * (nib & 3u))) & 0xFFu, o1 = (cw >> (8 * (nib >> 2))) & 0xFFu;
-                        const float d0 = bf2f(*reinterpret_cast<const uint16_t*>(row + o0 * 2));
-                        const float d1 = bf2f(*reinterpret_cast<const uint16_t*>(row + o1 * 2));
-                        const float ya = bf2f(yk & 0xFFFFu), yb = bf2f(yk >> 16);
-                        const float ga = 2.0f * d0 * (ya > 0.0f ? ya : 0.0f), gb = 2.0f * d1 * (yb > 0.0f ? yb : 0.0f);
-                        v = f2bf(ga) | (f2bf(gb) << 16);
-                        if (valid) *reinterpret_cast<uint32_t*>(ep.vals + tg * (F / 4) + blk_g * 2) = v;
+                        *reinterpret_cast<uint16_t*>(ttile + (bl * 8 + o0) * EP + t * 2) = (uint16_t)(v & 0xFFFFu);
+                        *reinterpret_cast<uint16_t*>(ttile + (bl * 8 + o1) * EP + t * 2) = (uint16_t)(v >> 16);
                     }
-                    // the same block as two plain 2:4 groups (blocked operand of eq. (3) / eq. (7))
-                    uint32_t a24, b24, mb8;
-                    vnm_block_to_24(v, nib, cw, a24, b24, mb8);
-                    uint32_t m4 = mb8 | ((uint32_t)__shfl_down((int)mb8, 1, 64) << 8);
-                    m4 |= (uint32_t)__shfl_down((int)m4, 2, 64) << 16;
-                    if (valid) {
-                        *reinterpret_cast<uint2*>(ep.v24 + blk_off(tg, blk_g * 4, F / 64)) = make_uint2(a24, b24);
-                        if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(ep.m24 + mblk_off(tg, blk_g * 8, F / 64)) = m4;
-                    }
-                    // dense transposed tile for the weight-gradient GEMM: row = hidden unit, column = token
-                    const uint32_t o0 = (cw >> (8 * (nib & 3u))) & 0xFFu, o1 = (cw >> (8 * (nib >> 2))) & 0xFFu;
-                    *reinterpret_cast<uint16_t*>(ttile + (bl * 8 + o0) * EP + t * 2) = (uint16_t)(v & 0xFFFFu);
-                    *reinterpret_cast<uint16_t*>(ttile + (bl * 8 + o1) * EP + t * 2) = (uint16_t)(v >> 16);
                 }
-                __syncthreads();
+                wave_lds_sync();
 #pragma unroll
                 for (int q = 0; q < 8; ++q) {          // 4 groups of 16 hidden units x 2 chunks of 32 tokens, 1 KB each
                     const int fr = (q >> 1) * 16 + (lane >> 2), tc = (q & 1) * 32 + (lane & 3) * 8;
@@ -380,7 +395,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         *reinterpret_cast<uint4*>(ep.at + blk_off(f0 + fr, t0 + tc, Rb / 32)) = *reinterpret_cast<const uint4*>(ttile + fr * EP + tc * 2);
                 }
             }
-            __syncthreads();
+            wave_lds_sync();
         }
     } else {
         constexpr int EP = WN * 2 + 16;

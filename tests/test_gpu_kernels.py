@@ -165,14 +165,16 @@ def _teacher_forced_step_check(T, D, F, mode, seed):
     assert_gemm_close(s["y1"], oracle.spmm24(inp["X"], s["w1_vals"], s["w1_meta"], inp["b1"]), "y1")
     yv, ym, yc = oracle.sqrelu_vnm_compress(s["y1"])
     assert np.array_equal(s["colidx"], yc) and np.array_equal(s["y2_meta"], ym) and np.array_equal(s["y2_vals"], yv)
-    # y1 at the kept slots: gather from the GPU's dense y1 with the oracle's own metadata
+    # y1 at the kept slots (stored in runs of 64 tokens x 8 column blocks): gather from the GPU's dense y1 with
+    # the oracle's own metadata
     ones = np.arange(1, yv.size + 1, dtype=np.uint32).reshape(yv.shape)
     slot_of = oracle.vnm_decompress((ones & 0xFFFF).astype(np.uint16), ym, yc).astype(np.int64) \
         + (oracle.vnm_decompress((ones >> 16).astype(np.uint16), ym, yc).astype(np.int64) << 16)
     want_kept = np.zeros(yv.size, dtype=np.uint16)
     tt, ff = np.nonzero(slot_of)
     want_kept[slot_of[tt, ff] - 1] = s["y1"][tt, ff]
-    assert np.array_equal(s["y1_kept"].reshape(-1), want_kept)
+    want_kept = want_kept.reshape(T // 64, 64, F // 64, 8, 2).transpose(0, 2, 1, 3, 4)       # [tb, fb, t, blk, 2]
+    assert np.array_equal(s["y1_kept"].reshape(-1), want_kept.reshape(-1))
     assert_gemm_close(to_bits(Y3), oracle.vnm_spmm(yv, ym, yc, inp["W2"], 0), "y3")
     rv2, rm2 = oracle.prune24_compress(np.ascontiguousarray(inp["W2"].T), mode)
     assert np.array_equal(s["w2t_vals"], rv2) and np.array_equal(s["w2t_meta"], rm2)
