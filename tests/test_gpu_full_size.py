@@ -1,0 +1,102 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times (dense y1 / dy2 not
+stored).  The run that keeps y1 / dy2 must give bit-identical results; from it the compressors are checked bit
+for bit (in full at the 1B shape, on slices of whole token blocks at the 7B shape) and the GEMM outputs on
+seeded samples of rows / columns that the oracle computes one by one, all teacher-forced."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_06183_amd as sffn
+from tests.util import to_dev, to_bits, assert_gemm_close
+from workload import CONFIGS, make_ffn_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(dev, T, D, F, keep):
+    step = sffn.FfnStep(T, D, F, sffn.MODE_HARD, keep_dense=keep)
+    outs = step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    torch.cuda.synchronize()
+    return step, outs
+
+
+@pytest.mark.parametrize("name,tb_slices", [("1b", None), ("7b", [(0, 2), (101, 103)]), ("70b", [(0, 1), (77, 78)]),
+                                            ("moe_expert", [(0, 1), (30, 31)])])
+def test_full_size_step(name, tb_slices):
+    T, D, F = CONFIGS[name]
+    inp = make_ffn_inputs(T, D, F, seed=0)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    packed_keys = ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta", "y2_vals", "y2_meta", "colidx", "dy1_vals", "y1_kept")
+
+    step0, outs0 = _run(dev, T, D, F, keep=False)              # what bench.py times
+    fast = [to_bits(t).copy() for t in outs0] + [to_bits(step0.saved()[k]).copy() for k in packed_keys]
+    del step0, outs0
+    torch.cuda.empty_cache()
+    step, outs = _run(dev, T, D, F, keep=True)
+    sv = step.saved()
+    full = [to_bits(t) for t in outs] + [to_bits(sv[k]) for k in packed_keys]
+    for a, b in zip(fast, full):
+        assert np.array_equal(a, b)
+    del fast
+    Y3, dX, dW1, dW2 = full[:4]
+    w1v, w1m, w2v, w2m, yv, ym, yc, dv, _ = full[4:]
+    y1, dy2 = to_bits(sv["y1"]), to_bits(sv["dy2"])
+    rng = np.random.default_rng(123)
+
+    # 2:4 weights: bit-exact, everywhere at 1b, on two bands of 1024 rows at the larger shapes (rows are independent)
+    for r in ([slice(0, F)] if tb_slices is None else [slice(0, 1024), slice(F - 1024, F)]):
+        rv, rm = oracle.prune24_compress(inp["W1"][r])
+        assert np.array_equal(w1v[r], rv) and np.array_equal(w1m[r], rm)
+        rv, rm = oracle.prune24_compress(np.ascontiguousarray(inp["W2"][:, r].T))
+        assert np.array_equal(w2v[r], rv) and np.array_equal(w2m[r], rm)
+    del rv, rm
+
+    # eq. (1) and eq. (4) on sampled token rows
+    rows = np.sort(rng.choice(T, 48, replace=False))
+    assert_gemm_close(y1[rows], oracle.spmm24(inp["X"][rows], w1v, w1m, inp["b1"]), "y1 rows")
+    assert_gemm_close(dy2[rows], oracle.spmm24(inp["dY"][rows], w2v, w2m, None), "dy2 rows")
+
+    # compressors: bit-exact on whole 64-token blocks (all of them at 1b)
+    slices = [(0, T // 64)] if tb_slices is None else tb_slices
+    for b0, b1 in slices:
+        r = slice(64 * b0, 64 * b1)
+        ov, om, oc = oracle.sqrelu_vnm_compress(y1[r])
+        assert np.array_equal(yc[b0:b1], oc) and np.array_equal(ym[r], om) and np.array_equal(yv[r], ov)
+        assert np.array_equal(dv[r], oracle.dsqrelu_vnm(dy2[r], y1[r], om, oc))
+    zero_frac = float(np.mean(oracle.sqrelu(y1[:2048]) == 0))
+    assert abs(zero_frac - 0.9) < 0.01
+
+    # eq. (3), (7): sampled token rows (a row only needs its own 64-token block's column indices)
+    def dense_rows(vals, rws):
+        out = np.zeros((len(rws), F), dtype=np.uint16)
+        for n, t in enumerate(rws):
+            tb = t // 64
+            blk = oracle.vnm_decompress(vals[64 * tb:64 * tb + 64], ym[64 * tb:64 * tb + 64], yc[tb:tb + 1])
+            out[n] = blk[t % 64]
+        return out
+
+    rows = np.sort(rng.choice(T, 32, replace=False))
+    assert_gemm_close(Y3[rows], oracle.dense_nt(dense_rows(yv, rows), inp["W2"]), "y3 rows")
+    assert_gemm_close(dX[rows], oracle.dense_nt(dense_rows(dv, rows), np.ascontiguousarray(inp["W1"].T)), "dX rows")
+
+    # eq. (5), (8): sampled hidden units f = 8 whole column blocks
+    blks = np.sort(rng.choice(F // 8, 8, replace=False))
+    cols = (blks[:, None] * 8 + np.arange(8)[None, :]).reshape(-1)
+
+    def dense_cols(vals):
+        # the [T, 64] slab of the V:N:M matrix restricted to the sampled column blocks
+        sub_v = vals.reshape(T, F // 8, 2)[:, blks].reshape(T, -1)
+        nib = np.empty((T, F // 8), dtype=np.uint8)
+        nib[:, 0::2] = ym & 0xF
+        nib[:, 1::2] = ym >> 4
+        sub_n = nib[:, blks]
+        sub_m = (sub_n[:, 0::2] | (sub_n[:, 1::2] << 4)).astype(np.uint8)
+        return oracle.vnm_decompress(np.ascontiguousarray(sub_v), sub_m, np.ascontiguousarray(yc[:, blks]))
+
+    a = oracle.bits_to_f64(dense_cols(yv))
+    ref = oracle.f64_to_bits(a.T @ oracle.bits_to_f64(inp["dY"]))              # [64, D]
+    assert_gemm_close(np.ascontiguousarray(dW2[:, cols].T), ref, "dW2 columns")
+    a = oracle.bits_to_f64(dense_cols(dv))
+    ref = oracle.f64_to_bits(a.T @ oracle.bits_to_f64(inp["X"]))
+    assert_gemm_close(dW1[cols], ref, "dW1 rows")
