@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--zero-fraction", type=float, default=0.90)
     ap.add_argument("--mode", default="hard", choices=["hard", "soft"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (reference kernel for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the step shards by tokens; no multi-GPU path is built). Use --gpus 1.")
@@ -103,6 +105,14 @@ def main():
             fn()
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / n
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         sparse_step()
