@@ -44,7 +44,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="1b", help="tiny | 1b | 7b | 70b | moe_expert")
+    ap.add_argument("--workload", default="1b", help="tiny | 1b | 7b | 70b | moe_expert | moe (8 experts, 16384 tokens routed top-2, grouped launches)")
     ap.add_argument("--zero-fraction", type=float, default=0.90)
     ap.add_argument("--mode", default="hard", choices=["hard", "soft"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -57,12 +57,19 @@ def main():
     import numpy as np
     import torch
     import paper_2602_06183_amd as sffn
-    from workload import CONFIGS, make_ffn_inputs
+    from workload import CONFIGS, make_ffn_inputs, make_moe_inputs
 
     sffn.load()                     # fails loudly when the HIP library is missing
-    T, D, F = CONFIGS[args.workload]
     mode = sffn.MODE_SOFT if args.mode == "soft" else sffn.MODE_HARD
-    inp = make_ffn_inputs(T, D, F, seed=0, zero_fraction=args.zero_fraction)
+    moe = args.workload == "moe"
+    if moe:
+        _, D, F = CONFIGS["moe_expert"]
+        inp = make_moe_inputs(16384, 8, 2, D, F, seed=0, zero_fraction=args.zero_fraction)
+        seg = [int(v) for v in inp["seg"]]
+        T = int(inp["counts"].sum())            # flop are counted on routed tokens, not on the 64-row padding
+    else:
+        T, D, F = CONFIGS[args.workload]
+        inp = make_ffn_inputs(T, D, F, seed=0, zero_fraction=args.zero_fraction)
 
     def dev(a):
         if a.dtype == np.uint16:
@@ -70,7 +77,7 @@ def main():
         return torch.from_numpy(a).cuda()
 
     X, W1, W2, b1, dY = (dev(inp[k]) for k in ("X", "W1", "W2", "b1", "dY"))
-    step = sffn.FfnStep(T, D, F, mode)
+    step = sffn.FfnStepGrouped(seg, D, F, mode) if moe else sffn.FfnStep(T, D, F, mode)
     flops = 12.0 * T * D * F
 
     # ---- dense bf16 FFN step on hipBLASLt (torch.matmul), same shapes, same process -------------
@@ -79,21 +86,31 @@ def main():
     except Exception:
         pass
     b1h = b1.to(torch.bfloat16)
-    y1 = torch.empty((T, F), dtype=torch.bfloat16, device="cuda")
+    Tp = X.shape[0]                                       # rows including padding
+    y1 = torch.empty((Tp, F), dtype=torch.bfloat16, device="cuda")
     y2, dy2, dy1 = torch.empty_like(y1), torch.empty_like(y1), torch.empty_like(y1)
-    y3, dXd = torch.empty((T, D), dtype=torch.bfloat16, device="cuda"), torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+    y3, dXd = torch.empty((Tp, D), dtype=torch.bfloat16, device="cuda"), torch.empty((Tp, D), dtype=torch.bfloat16, device="cuda")
     dW1d, dW2d = torch.empty_like(W1), torch.empty_like(W2)
-    W1t, W2t = W1.t(), W2.t()
 
-    def dense_step():
-        torch.addmm(b1h, X, W1t, out=y1)                 # eq. (1)
+    def dense_ffn(X, W1, W2, b1h, dY, y1, y2, y3, dy2, dy1, dXd, dW1d, dW2d):
+        torch.addmm(b1h, X, W1.t(), out=y1)              # eq. (1)
         torch.clamp_min(y1, 0.0, out=y2); y2.mul_(y2)             # eq. (2)
-        torch.mm(y2, W2t, out=y3)                        # eq. (3)
+        torch.mm(y2, W2.t(), out=y3)                     # eq. (3)
         torch.mm(dY, W2, out=dy2)                        # eq. (4)
         torch.mm(dY.t(), y2, out=dW2d)                   # eq. (5)
         torch.clamp_min(y1, 0.0, out=dy1); dy1.mul_(dy2).mul_(2.0) # eq. (6)
         torch.mm(dy1, W1, out=dXd)                       # eq. (7)
         torch.mm(dy1.t(), X, out=dW1d)                   # eq. (8)
+
+    if moe:     # the dense MoE layer: the same eight calls per expert on its segment
+        parts = [tuple(t[seg[e]:seg[e + 1]] for t in (X, dY, y1, y2, y3, dy2, dy1, dXd)) for e in range(len(seg) - 1)]
+
+        def dense_step():
+            for e, (Xe, dYe, y1e, y2e, y3e, dy2e, dy1e, dXe) in enumerate(parts):
+                dense_ffn(Xe, W1[e], W2[e], b1h[e], dYe, y1e, y2e, y3e, dy2e, dy1e, dXe, dW1d[e], dW2d[e])
+    else:
+        def dense_step():
+            dense_ffn(X, W1, W2, b1h, dY, y1, y2, y3, dy2, dy1, dXd, dW1d, dW2d)
 
     def sparse_step():
         step(X, W1, W2, b1, dY)
@@ -150,6 +167,27 @@ def main():
                 "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
                 "issued": round(exe / (avg_ms * 1e-3) / 1e12, 2), "issued_frac": round(exe / (avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
+    # ---- the two compressors alone (HBM-bound; algorithmic bytes = input read once + packed outputs) -----------
+    def gbs(fn, nbytes, n=10):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)   # the binding launches on torch's current stream
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return round(nbytes / (e0.elapsed_time(e1) * 1e-3 / n) / 1e9, 1)
+
+    w1_one, w2_one = (W1[0], W2[0]) if moe else (W1, W2)
+    y1_one = y1[:min(Tp, 16384)]
+    kernels = {
+        "prune24_compress(W1) GB/s": gbs(lambda: sffn.prune24_compress(w1_one, False, mode), 3.125 * F * D),
+        "prune24_compress(W2, trans) GB/s": gbs(lambda: sffn.prune24_compress(w2_one, True, mode), 3.125 * F * D),
+        "sqrelu_vnm_compress GB/s": gbs(lambda: sffn.sqrelu_vnm_compress(y1_one), (2 + 0.5 + 0.0625 + 1.0 / 128) * y1_one.shape[0] * F),
+        "hbm_peak GB/s": HBM_PEAK_GBS,
+    }
+
     # ---- CPU oracle on the host cores: a bounded token sample of the same workload ---------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -160,11 +198,13 @@ def main():
         except Exception:
             cores = os.cpu_count()
         Ts = min(T, max(64, (int(3.0e11 / (12.0 * D * F)) // 64) * 64))      # about 0.3 TFLOP of fp64 matmul
+        w1o, w2o, b1o = (inp[k][0] if moe else inp[k] for k in ("W1", "W2", "b1"))    # moe: expert 0 on its first tokens
         t0 = time.perf_counter()
-        oracle.ffn_sparse_step_ref(inp["X"][:Ts], inp["W1"], inp["W2"], inp["b1"], inp["dY"][:Ts], mode)
+        oracle.ffn_sparse_step_ref(inp["X"][:Ts], w1o, w2o, b1o, inp["dY"][:Ts], mode)
         dt = time.perf_counter() - t0
         cpu = {"value": round(12.0 * Ts * D * F / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-               "sample": "oracle.ffn_sparse_step_ref on the first %d of %d tokens (same D, F, weights), %.1f s" % (Ts, T, dt)}
+               "sample": "oracle.ffn_sparse_step_ref on the first %d of %d tokens (same D, F, weights%s), %.1f s"
+                         % (Ts, T, " of expert 0" if moe else "", dt)}
 
     value = flops / (ms_sparse * 1e-3) / 1e12
     out = {
@@ -172,14 +212,18 @@ def main():
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_sparse, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s: one FFN layer, T=%d tokens, d_model=%d, d_ff=%d, 2:4 weights (%s), V:N:M 64:2:8 SquaredReLU, zero fraction %.2f, seed 0"
-                   % (args.workload, T, D, F, args.mode, args.zero_fraction)},
+        "config": {"workload": ("moe: 8 experts, 16384 tokens routed top-2 = %d token slots in segments %s (64-row aligned), d_model=%d, d_ff=%d per expert, "
+                                "2:4 weights (%s), V:N:M 64:2:8 SquaredReLU, zero fraction %.2f, seed 0; one grouped launch per stage"
+                                % (T, seg, D, F, args.mode, args.zero_fraction)) if moe else
+                               "%s: one FFN layer, T=%d tokens, d_model=%d, d_ff=%d, 2:4 weights (%s), V:N:M 64:2:8 SquaredReLU, zero fraction %.2f, seed 0"
+                               % (args.workload, T, D, F, args.mode, args.zero_fraction)},
         "frac_of_mfma_peak": round(value / MFMA_BF16_PEAK_TFLOPS, 4),
         "dense_ms_per_step": round(ms_dense, 4), "dense_tflops": round(flops / (ms_dense * 1e-3) / 1e12, 2),
         "dense_frac_of_mfma_peak": round(flops / (ms_dense * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
         "speedup_vs_dense": round(ms_dense / ms_sparse, 4),
         "second_pass": {"ms_per_step": round(ms_sparse2, 4), "dense_ms_per_step": round(ms_dense2, 4)},
         "stage_ms": {k: round(v, 4) for k, v in acc.items()},
+        "standalone_kernels": kernels,
         "roofline": roofline, "cpu_baseline": cpu,
         "paper_context": "paper reports 1.4-1.5x for 2:4 GEMMs and 1.4-1.7x end-to-end on NVIDIA sparse tensor cores (Sections 1, 5.2.3); context, not a target",
     }

@@ -136,6 +136,21 @@ int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, 
                     const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
                     uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
 
+/* Mixture-of-experts form of the step (Section 1 states the method carries over to MoE FFNs; every expert is
+ * one Alg. 1 + Alg. 2 FFN): n_experts (1..64) experts with their own weights, each applied to one consecutive
+ * segment of the T token rows.  seg_offsets is a HOST array of n_experts + 1 ascending multiples of 64 with
+ * seg_offsets[0] = 0 and seg_offsets[n_experts] = cfg->T (it is read during the call, not afterwards); a segment
+ * may be empty, its expert then gets zero weight gradients.  Rows the caller pads a segment with must be zero in X
+ * and dY.  X, dY, Y3, dX: [T, D]; W1, dW1: [n_experts, F, D]; W2, dW2: [n_experts, D, F]; b1: [n_experts, F] or NULL.
+ * Every stage is a single launch over all experts.  The workspace has the layout of ffn_sparse_step with every
+ * weight-shaped tensor holding n_experts matrices back to back (sffn_grouped_workspace_layout()).  The router,
+ * the token permutation and the weighted combine of an MoE layer are outside this library. */
+size_t sffn_grouped_workspace_bytes(const sffn_cfg* cfg, int n_experts);
+int    sffn_grouped_workspace_layout(const sffn_cfg* cfg, int n_experts, sffn_ws_layout* out);
+int ffn_sparse_step_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* seg_offsets, const uint16_t* X,
+                            const uint16_t* W1, const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3,
+                            uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
+
 /* Measurement aid (not part of the method): when enabled, ffn_sparse_step records a HIP event on the
  * caller's stream behind every kernel launch.  sffn_profile_read() waits for the last event of the
  * most recent step and returns the number of launches, filling ms[i] (duration of launch i) and

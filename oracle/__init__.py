@@ -13,4 +13,4 @@ from .sparse24 import (prune24_positions, prune24_compress, prune24_decompress,
 from .vnm import (sqrelu, vnm_select_columns, vnm_compress, vnm_decompress,
                   sqrelu_vnm_compress, dsqrelu_vnm, vnm_to_24)
 from .gemm import spmm24, vnm_spmm, vnm_wgrad, dense_nt
-from .ffn import ffn_sparse_step_ref, ffn_dense_ref
+from .ffn import ffn_sparse_step_ref, ffn_dense_ref, ffn_sparse_step_grouped_ref

@@ -51,3 +51,18 @@ def ffn_dense_ref(X, W1, W2, b1, dY):
     dX = dense_nt(dy1, np.ascontiguousarray(np.asarray(W1).T))
     dW1 = dense_nt(np.ascontiguousarray(dy1.T), np.ascontiguousarray(np.asarray(X).T))
     return dict(y1=y1, y2=y2, y3=y3, dy2=dy2, dy1=dy1, dW2=dW2, dX=dX, dW1=dW1)
+
+
+def ffn_sparse_step_grouped_ref(X, W1, W2, b1, dY, seg_offsets, mode=HARD, V=64, M=8):
+    """Mixture-of-experts form (Section 1: the method applies to MoE FFNs, each expert being one FFN of
+    Alg. 1 / Alg. 2): expert e owns rows seg_offsets[e]..seg_offsets[e+1] of X and dY and its own
+    W1[e] [F, D], W2[e] [D, F], b1[e] [F].  Returns a list with one ffn_sparse_step_ref result per expert
+    (None for an expert without rows; its weight gradients are zero by the empty sum)."""
+    res = []
+    for e in range(len(seg_offsets) - 1):
+        a, b = int(seg_offsets[e]), int(seg_offsets[e + 1])
+        if b == a:
+            res.append(None)
+            continue
+        res.append(ffn_sparse_step_ref(X[a:b], W1[e], W2[e], None if b1 is None else b1[e], dY[a:b], mode, V, M))
+    return res

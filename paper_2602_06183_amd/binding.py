@@ -59,6 +59,10 @@ def load():
     lib.dsqrelu_vnm.argtypes = [p, p, p, p, i64, i64, i32, i32, p, p]
     lib.vnm_wgrad.argtypes = [p, p, p, p, i64, i64, i64, i32, i32, i32, p, p, sz, p]
     lib.ffn_sparse_step.argtypes = [ctypes.POINTER(_Cfg)] + [p] * 9 + [p, sz, p]
+    lib.sffn_grouped_workspace_bytes.restype = sz
+    lib.sffn_grouped_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg), i32]
+    lib.sffn_grouped_workspace_layout.argtypes = [ctypes.POINTER(_Cfg), i32, ctypes.POINTER(_Layout)]
+    lib.ffn_sparse_step_grouped.argtypes = [ctypes.POINTER(_Cfg), i32, ctypes.POINTER(ctypes.c_int64)] + [p] * 9 + [p, sz, p]
     lib.sffn_profile_enable.argtypes = [i32]
     lib.sffn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_char_p), i32]
     lib.sffn_tune.argtypes = [i32, i32]
@@ -225,6 +229,47 @@ class FfnStep:
 
         return dict(w1_vals=view(L["w1_vals"], (F, D // 2), torch.bfloat16), w1_meta=view(L["w1_meta"], (F, D // 8), torch.uint8),
                     w2t_vals=view(L["w2t_vals"], (F, D // 2), torch.bfloat16), w2t_meta=view(L["w2t_meta"], (F, D // 8), torch.uint8),
+                    y1=view(L["y1"], (T, F), torch.bfloat16), y2_vals=view(L["y2_vals"], (T, F // 4), torch.bfloat16),
+                    y2_meta=view(L["y2_meta"], (T, F // 16), torch.uint8), colidx=view(L["colidx"], (T // 64, F // 8, 4), torch.uint8),
+                    dy2=view(L["dy2"], (T, F), torch.bfloat16), dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16),
+                    y1_kept=view(L["y1_kept"], (T, F // 4), torch.bfloat16))
+
+
+class FfnStepGrouped:
+    """Pre-allocated outputs and workspace for ffn_sparse_step_grouped: n_experts FFNs, expert e on token rows
+    seg[e]..seg[e+1] (host integers, multiples of 64; T = seg[-1])."""
+
+    def __init__(self, seg, D, F, mode=MODE_HARD, device="cuda", keep_dense=False):
+        self.seg = [int(v) for v in seg]
+        self.E, self.T, self.D, self.F, self.mode = len(self.seg) - 1, self.seg[-1], D, F, mode
+        self.seg_c = (ctypes.c_int64 * len(self.seg))(*self.seg)
+        self.cfg = _cfg(self.T, D, F, mode, flags=FLAG_KEEP_DENSE if keep_dense else 0)
+        lay = _Layout()
+        _check(load().sffn_grouped_workspace_layout(ctypes.byref(self.cfg), self.E, ctypes.byref(lay)))
+        self.layout = {n: getattr(lay, n) for n, _ in _Layout._fields_}
+        self.ws = _u8((self.layout["total"],), device)
+        self.Y3, self.dX = _bf16((self.T, D), device), _bf16((self.T, D), device)
+        self.dW1, self.dW2 = _bf16((self.E, F, D), device), _bf16((self.E, D, F), device)
+
+    def __call__(self, X, W1, W2, b1, dY):
+        _check(load().ffn_sparse_step_grouped(ctypes.byref(self.cfg), self.E, self.seg_c, _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1),
+                                              _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws),
+                                              self.layout["total"], _stream()))
+        return self.Y3, self.dX, self.dW1, self.dW2
+
+    def saved(self):
+        """As FfnStep.saved(); weight-shaped tensors carry a leading expert axis."""
+        T, D, F, E, L = self.T, self.D, self.F, self.E, self.layout
+
+        def view(off, shape, dtype):
+            n = 1
+            for s in shape:
+                n *= s
+            nbytes = n * (2 if dtype == torch.bfloat16 else 1)
+            return self.ws[off:off + nbytes].view(dtype).view(shape)
+
+        return dict(w1_vals=view(L["w1_vals"], (E, F, D // 2), torch.bfloat16), w1_meta=view(L["w1_meta"], (E, F, D // 8), torch.uint8),
+                    w2t_vals=view(L["w2t_vals"], (E, F, D // 2), torch.bfloat16), w2t_meta=view(L["w2t_meta"], (E, F, D // 8), torch.uint8),
                     y1=view(L["y1"], (T, F), torch.bfloat16), y2_vals=view(L["y2_vals"], (T, F // 4), torch.bfloat16),
                     y2_meta=view(L["y2_meta"], (T, F // 16), torch.uint8), colidx=view(L["colidx"], (T // 64, F // 8, 4), torch.uint8),
                     dy2=view(L["dy2"], (T, F), torch.bfloat16), dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16),

@@ -45,25 +45,27 @@ struct FullLayout {
     size_t w1_vblk, w1_mblk, w2t_vblk, w2t_mblk, x_blk, xt_blk, dy_blk, dyt_blk, w2_blk, w1t_blk, a24_vblk, a24_mblk, at_blk, total;
 };
 
-bool make_layout(const sffn_cfg* c, FullLayout* L) {
-    if (!c || !mult64(c->T) || !mult64(c->D) || !mult64(c->F)) return false;
-    const size_t T = c->T, D = c->D, F = c->F;
+// E = number of experts (1 for the plain step): every weight-shaped tensor holds E matrices back to back.
+bool make_layout(const sffn_cfg* c, FullLayout* L, int n_experts = 1) {
+    if (!c || !mult64(c->T) || !mult64(c->D) || !mult64(c->F) || n_experts < 1) return false;
+    const size_t T = c->T, D = c->D, F = (size_t)c->F * n_experts;   // F only sizes weight-shaped tensors below ...
+    const size_t TF = T * (size_t)c->F;                               // ... token x hidden tensors use TF
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
     L->pub.w1_vals = take(F * D);          L->pub.w1_meta = take(F * D / 8);
     L->pub.w2t_vals = take(F * D);         L->pub.w2t_meta = take(F * D / 8);
-    L->pub.y1 = take(T * F * 2);
-    L->pub.y2_vals = take(T * F / 2);      L->pub.y2_meta = take(T * F / 16);   L->pub.colidx = take(T / 64 * (F / 8) * 4);
-    L->pub.dy2 = take(T * F * 2);
-    L->pub.dy1_vals = take(T * F / 2);
-    L->pub.y1_kept = take(T * F / 2);
+    L->pub.y1 = take(TF * 2);
+    L->pub.y2_vals = take(TF / 2);      L->pub.y2_meta = take(TF / 16);   L->pub.colidx = take(TF / 64 / 8 * 4);
+    L->pub.dy2 = take(TF * 2);
+    L->pub.dy1_vals = take(TF / 2);
+    L->pub.y1_kept = take(TF / 2);
     L->w1_vblk = take(F * D);              L->w1_mblk = take(F * D / 8);
     L->w2t_vblk = take(F * D);             L->w2t_mblk = take(F * D / 8);
     L->x_blk = take(T * D * 2);            L->xt_blk = take(D * T * 2);
     L->dy_blk = take(T * D * 2);           L->dyt_blk = take(D * T * 2);
     L->w2_blk = take(D * F * 2);           L->w1t_blk = take(D * F * 2);
-    L->a24_vblk = take(T * F);             L->a24_mblk = take(T * F / 8);
-    L->at_blk = take(F * T * 2);
+    L->a24_vblk = take(TF);             L->a24_mblk = take(TF / 8);
+    L->at_blk = take(TF * 2);
     L->total = off;
     L->pub.total = off;
     return true;
@@ -209,21 +211,34 @@ int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_co
     return SFFN_OK;
 }
 
-int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, const uint16_t* W2, const float* b1,
-                    const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace,
-                    size_t ws_bytes, void* stream) {
+// Alg. 1 + Alg. 2 for n_experts independent FFNs over consecutive token segments (n_experts = 1, seg = nullptr:
+// the plain step).  Every stage is one launch; the GEMMs find their expert from the segment table.
+static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, const uint16_t* X, const uint16_t* W1,
+                    const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
+                    uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
     REQUIRE(cfg && X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_sparse_step: null pointer");
     FullLayout L;
-    REQUIRE(make_layout(cfg, &L), SFFN_EINVAL, "ffn_sparse_step: T, D, F must be positive multiples of 64");
+    REQUIRE(n_experts >= 1 && n_experts <= GemmGroup::kMaxExperts, SFFN_EINVAL, "ffn_sparse_step_grouped: n_experts must be in 1..64");
+    REQUIRE(make_layout(cfg, &L, n_experts), SFFN_EINVAL, "ffn_sparse_step: T, D, F must be positive multiples of 64");
     REQUIRE(cfg->V == 64 && cfg->M == 8, SFFN_EUNSUPPORTED, "ffn_sparse_step: only V=64, M=8 is built");
     REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_sparse_step: unknown mode");
     REQUIRE(aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(b1) && aligned16(dY) && aligned16(Y3) && aligned16(dX) &&
                 aligned16(dW1) && aligned16(dW2) && aligned16(workspace),
             SFFN_EINVAL, "ffn_sparse_step: pointers must be 16-byte aligned");
-    REQUIRE(cfg->T < 65536 && fits_int(cfg->F) && fits_int(cfg->D), SFFN_EUNSUPPORTED, "ffn_sparse_step: T must be below 65536");
+    REQUIRE(cfg->T < 65536 && fits_int(cfg->F * n_experts) && fits_int(cfg->D), SFFN_EUNSUPPORTED,
+            "ffn_sparse_step: T must be below 65536 and F * n_experts below 2^31");
     REQUIRE(workspace && ws_bytes >= L.total, SFFN_EWORKSPACE, "ffn_sparse_step: workspace missing or too small");
+    const int64_t T = cfg->T, D = cfg->D, F = cfg->F, E = n_experts;
+    GemmGroup g;                                    // g.n = 0: plain step
+    if (seg) {
+        REQUIRE(seg[0] == 0 && seg[E] == T, SFFN_EINVAL, "ffn_sparse_step_grouped: seg_offsets must start at 0 and end at T");
+        for (int e = 0; e < E; ++e)
+            REQUIRE(seg[e + 1] >= seg[e] && seg[e + 1] % 64 == 0, SFFN_EINVAL,
+                    "ffn_sparse_step_grouped: seg_offsets must be ascending multiples of 64");
+        g.n = (int)E;
+        for (int e = 0; e <= E; ++e) g.seg[e] = (int32_t)seg[e];
+    }
 
-    const int64_t T = cfg->T, D = cfg->D, F = cfg->F;
     hipStream_t s = (hipStream_t)stream;
     unsigned char* ws = (unsigned char*)workspace;
     uint16_t* w1v = (uint16_t*)(ws + L.pub.w1_vals);    uint8_t* w1m = ws + L.pub.w1_meta;
@@ -241,6 +256,14 @@ int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, 
     uint16_t* atb = (uint16_t*)(ws + L.at_blk);
     uint16_t* ykept = (uint16_t*)(ws + L.pub.y1_kept);
     const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
+    // the three ways a token segment meets its expert's weights (see GemmGroup)
+    GemmGroup g_packed = g, g_dense = g, g_wgrad = g;
+    g_packed.role = 1; g_packed.a_stride = F * D / 2; g_packed.m_stride = F * D / 8; g_packed.bias_stride = F;
+    g_dense.role = 0;  g_dense.b_stride = D * F;
+    g_wgrad.role = 2;  g_wgrad.out_stride = D * F;
+    const GemmGroup* gp = g.n ? &g_packed : nullptr;
+    const GemmGroup* gd = g.n ? &g_dense : nullptr;
+    const GemmGroup* gw = g.n ? &g_wgrad : nullptr;
 
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
     // Every GEMM operand is first brought into the blocked layout by the kernel that reads or produces it
@@ -248,28 +271,55 @@ int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, 
     // pruning pass, the activations by the fused epilogues of eqs. (1) and (4).
     // ---- Alg. 1 -------------------------------------------------------------------------------
     STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
-    STAGE(launch_prune24_step(W1, F, D, D, 0, cfg->mode, w1v, w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
+    // row pruning is per row, so the E stacked [F, D] matrices are one [E * F, D] matrix
+    STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, w1v, w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
     {   // eq. (1), then eq. (2) + V:N:M compression on the tile while it is still in LDS
         VnmEpilogue ep;
         ep.mode = 1; ep.store_dense = keep_dense; ep.vals = y2v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
         ep.v24 = a24v; ep.m24 = a24m; ep.at = atb;
-        STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s), "step/y1+sqrelu_vnm_compress");
+        STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s, gp), "step/y1+sqrelu_vnm_compress");
     }
-    STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, w2v, w2m, w2vb, w2mb, w2b, s), "step/prune24(W2.T)");
-    STAGE(launch_gemm_nt_blocked(1, a24v, a24m, w2b, nullptr, T, D, F, 0, Y3, D, s), "step/y3");            // eq. (3)
+    STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, w2v, w2m, w2vb, w2mb, w2b, s, (int)E), "step/prune24(W2.T)");
+    STAGE(launch_gemm_nt_blocked(1, a24v, a24m, w2b, nullptr, T, D, F, 0, Y3, D, s, gd), "step/y3");            // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
     STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
-    STAGE(launch_gemm_nt_blocked(0, atb, nullptr, dytb, nullptr, F, D, T, 1, dW2, F, s), "step/dW2");       // eq. (5)
+    STAGE(launch_gemm_nt_blocked(0, atb, nullptr, dytb, nullptr, F, D, T, 1, dW2, F, s, gw), "step/dW2");       // eq. (5)
     {   // eq. (4), then eq. (6) on y2's kept slots; overwrites the 2:4 view and the transposed tile with dy1's
         VnmEpilogue ep;
         ep.mode = 2; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
         ep.v24 = a24v; ep.m24 = a24m; ep.at = atb;
-        STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, ep, s), "step/dy2+dsqrelu_vnm");
+        STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, ep, s, gp), "step/dy2+dsqrelu_vnm");
     }
-    STAGE(launch_transpose(W1, F, D, D, w1tb, 1, nullptr, s), "step/W1.T");
-    STAGE(launch_gemm_nt_blocked(1, a24v, a24m, w1tb, nullptr, T, D, F, 0, dX, D, s), "step/dX");           // eq. (7)
-    STAGE(launch_gemm_nt_blocked(0, atb, nullptr, xtb, nullptr, F, D, T, 0, dW1, D, s), "step/dW1");        // eq. (8)
+    STAGE(launch_transpose(W1, F, D, D, w1tb, 1, nullptr, s, (int)E), "step/W1.T");
+    STAGE(launch_gemm_nt_blocked(1, a24v, a24m, w1tb, nullptr, T, D, F, 0, dX, D, s, gd), "step/dX");           // eq. (7)
+    STAGE(launch_gemm_nt_blocked(0, atb, nullptr, xtb, nullptr, F, D, T, 0, dW1, D, s, gw), "step/dW1");        // eq. (8)
     return SFFN_OK;
+}
+
+int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, const uint16_t* W2, const float* b1,
+                    const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace,
+                    size_t ws_bytes, void* stream) {
+    return run_step(cfg, 1, nullptr, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, ws_bytes, stream);
+}
+
+size_t sffn_grouped_workspace_bytes(const sffn_cfg* cfg, int n_experts) {
+    FullLayout L;
+    return make_layout(cfg, &L, n_experts) ? L.total : 0;
+}
+
+int sffn_grouped_workspace_layout(const sffn_cfg* cfg, int n_experts, sffn_ws_layout* out) {
+    FullLayout L;
+    REQUIRE(out != nullptr, SFFN_EINVAL, "sffn_grouped_workspace_layout: out is null");
+    REQUIRE(make_layout(cfg, &L, n_experts), SFFN_EINVAL, "sffn_grouped_workspace_layout: T, D, F must be positive multiples of 64, n_experts >= 1");
+    *out = L.pub;
+    return SFFN_OK;
+}
+
+int ffn_sparse_step_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* seg_offsets, const uint16_t* X, const uint16_t* W1,
+                            const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
+                            uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
+    REQUIRE(seg_offsets != nullptr, SFFN_EINVAL, "ffn_sparse_step_grouped: seg_offsets is null");
+    return run_step(cfg, n_experts, seg_offsets, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, ws_bytes, stream);
 }
 
 int sffn_tune(int key, int value) {

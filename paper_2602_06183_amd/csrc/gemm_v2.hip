@@ -84,7 +84,7 @@ template <bool SPARSE, bool OUT_I_CONTIG, int EPI>
 __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restrict__ a_vals, const uint8_t* __restrict__ a_meta,
                                                         const uint16_t* __restrict__ B, const float* __restrict__ bias,
                                                         int Ra, int Rb, int K, uint16_t* __restrict__ out, int64_t ldo,
-                                                        int tiles_m, int tiles_n, int blocked, VnmEpilogue ep) {
+                                                        int tiles_m, int tiles_n, int blocked, VnmEpilogue ep, GemmGroup grp) {
     static_assert(EPI == 0 || (SPARSE && OUT_I_CONTIG), "the V:N:M epilogues belong to the 2:4-weight GEMMs");
     using C = Cfg<SPARSE>;
     constexpr int BM = C::BM, BN = C::BN, WM = 128, WN = 64, FM = 4, FN = 2;
@@ -94,18 +94,52 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     const int wm = wave >> 2, wn = wave & 3;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    int tm, tn;
+    // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs; the remap gives each XCD a run of
+    // consecutive logical ids, and logical ids walk bands of 4 tile rows, so an XCD's L2 sees few operand panels.
+    int L;
     {
         const int n = gridDim.x, pid = blockIdx.x, per = n >> 3;
-        const int L = (pid < per * 8) ? (pid & 7) * per + (pid >> 3) : pid;
+        L = (pid < per * 8) ? (pid & 7) * per + (pid >> 3) : pid;
+    }
+    // Grouped form: find the expert of this tile and narrow the problem to its token segment.
+    const int Kld = K;                   // K extent of the stored operands (block-row stride); K becomes the loop length
+    const int tok_ld = grp.n ? grp.seg[grp.n] : Rb;       // tokens in the token-indexed outputs of the V:N:M epilogue
+    int i_base = 0, j_base = 0, k_base = 0;
+    if (grp.n) {
+        int e = 0;
+        if (grp.role == 2) {
+            const int per = tiles_m * tiles_n;
+            e = L / per;
+            L -= e * per;
+            k_base = grp.seg[e];
+            K = grp.seg[e + 1] - k_base;
+        } else {
+            const int other = grp.role == 0 ? tiles_n : tiles_m;
+            int cnt = 0;
+            for (; e < grp.n; ++e) {
+                cnt = ((grp.seg[e + 1] - grp.seg[e] + 255) >> 8) * other;
+                if (L < cnt) break;
+                L -= cnt;
+            }
+            if (e == grp.n) return;      // (the launcher sizes the grid exactly; kept as a guard)
+            if (grp.role == 0) { tiles_m = cnt / other; i_base = grp.seg[e]; Ra = grp.seg[e + 1]; }
+            else               { tiles_n = cnt / other; j_base = grp.seg[e]; Rb = grp.seg[e + 1]; }
+        }
+        if (grp.role != 0) { a_vals += e * grp.a_stride; if (SPARSE) a_meta += e * grp.m_stride; }
+        if (grp.role != 1) B += e * grp.b_stride;
+        if (bias) bias += e * grp.bias_stride;
+        out += e * grp.out_stride;
+    }
+    int tm, tn;
+    {
         constexpr int GROUP = 4;
         const int width = GROUP * tiles_n, group = L / width, first = group * GROUP;
         const int gsz = (tiles_m - first) < GROUP ? (tiles_m - first) : GROUP;
         tm = first + (L % width) % gsz;
         tn = (L % width) / gsz;
     }
-    const int i0 = tm * BM, j0 = tn * BN;
-    const int lda = SPARSE ? K / 2 : K;
+    const int i0 = i_base + tm * BM, j0 = j_base + tn * BN;
+    const int lda = SPARSE ? Kld / 2 : Kld;
 
     // ---- per-lane source addresses of the DMA loads.  A wave-wide load fills 1 KB of LDS = 16 tile rows x
     //      64 bytes; lane l lands at (row l / 4, 16-byte chunk l % 4) and therefore fetches the chunk that the
@@ -120,25 +154,26 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     {
         const int rb = lane >> 2;                                        // row inside the 16-row group
         const int c = (lane & 3) ^ ((rb >> 2) & 3);                      // source chunk for this lane's LDS slot
-        const int KCa = SPARSE ? K / 64 : K / 32, KCb = K / 32;          // 32-element chunks per row
+        const int KCa = SPARSE ? Kld / 64 : Kld / 32, KCb = Kld / 32;    // 32-element chunks per row
+        const int64_t ka = (int64_t)(SPARSE ? k_base / 64 : k_base / 32) << 9, kb = (int64_t)(k_base / 32) << 9;   // blocked only (grouped)
 #pragma unroll
         for (int n = 0; n < A_LD; ++n) {
             int gr = i0 + (wave * A_LD + n) * 16; gr = gr < Ra ? gr : Ra - 16;
-            a_base[n] = uniform64(blocked ? a_vals + ((int64_t)(gr >> 4) * KCa << 9) : a_vals + (int64_t)gr * lda);
+            a_base[n] = uniform64(blocked ? a_vals + ((int64_t)(gr >> 4) * KCa << 9) + ka : a_vals + (int64_t)gr * lda);
         }
 #pragma unroll
         for (int n = 0; n < B_LD; ++n) {
             // SPARSE: a stage holds 64 k of B as two half-tiles (k 0-31, k 32-63), each laid out like the A tile
             const int bk = wave * B_LD + n, h = SPARSE ? (bk >> 4) : 0;
             int gr = j0 + (bk & 15) * 16; gr = gr < Rb ? gr : Rb - 16;
-            b_base[n] = uniform64(blocked ? B + (((int64_t)(gr >> 4) * KCb + h) << 9) : B + (int64_t)gr * K + h * 32);
+            b_base[n] = uniform64(blocked ? B + (((int64_t)(gr >> 4) * KCb + h) << 9) + kb : B + (int64_t)gr * Kld + h * 32);
         }
         a_lane = blocked ? (rb * 32 + c * 8) * 2 : (uint32_t)(rb * lda + c * 8) * 2;
-        b_lane = blocked ? (rb * 32 + c * 8) * 2 : (uint32_t)(rb * K + c * 8) * 2;
-        m_lane = blocked ? lane * 4 : (uint32_t)((lane >> 1) * (K / 8) + (lane & 1) * 4);
+        b_lane = blocked ? (rb * 32 + c * 8) * 2 : (uint32_t)(rb * Kld + c * 8) * 2;
+        m_lane = blocked ? lane * 4 : (uint32_t)((lane >> 1) * (Kld / 8) + (lane & 1) * 4);
         if (SPARSE) {
             int gr = i0 + wave * 32; gr = gr < Ra ? gr : Ra - 32;
-            m_base = uniform64(blocked ? a_meta + ((int64_t)(gr >> 6) * (K / 64) << 9) + (gr & 63) * 8 : a_meta + (int64_t)gr * (K / 8));
+            m_base = uniform64(blocked ? a_meta + (((int64_t)(gr >> 6) * (Kld / 64) + k_base / 64) << 9) + (gr & 63) * 8 : a_meta + (int64_t)gr * (Kld / 8));
         }
         a_kstep = blocked ? 1024 : 64;
         b_kstep = blocked ? 1024 * (C::BK / 32) : C::BK * 2;
@@ -220,8 +255,9 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     };
 #define SB() __builtin_amdgcn_sched_barrier(0)
 
-    const int nk = K / C::BK;
+    const int nk = K / C::BK;            // 0 for an expert without tokens (weight gradients): the output is zeros
     constexpr int DIST = C::NSTAGE - 1;
+    if (nk > 0) {
 #pragma unroll
     for (int p = 0; p < DIST; ++p) issue(p < nk ? p : nk - 1, p);
     wait_vmcnt<(DIST - 1) * C::LOADS>();
@@ -261,6 +297,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     }
 #undef SB
     wait_vmcnt<0>();
+    }
     __syncthreads();
 
     if (OUT_I_CONTIG) {
@@ -399,7 +436,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                 for (int q = 0; q < 8; ++q) {          // 4 groups of 16 hidden units x 2 chunks of 32 tokens, 1 KB each
                     const int fr = (q >> 1) * 16 + (lane >> 2), tc = (q & 1) * 32 + (lane & 3) * 8;
                     if (valid)
-                        *reinterpret_cast<uint4*>(ep.at + blk_off(f0 + fr, t0 + tc, Rb / 32)) = *reinterpret_cast<const uint4*>(ttile + fr * EP + tc * 2);
+                        *reinterpret_cast<uint4*>(ep.at + blk_off(f0 + fr, t0 + tc, tok_ld / 32)) = *reinterpret_cast<const uint4*>(ttile + fr * EP + tc * 2);
                 }
             }
             wave_lds_sync();
@@ -430,43 +467,62 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     }
 }
 
+// Grid of a launch: one workgroup per 256 x 256 output tile; grouped: per expert, over its token segment.
+static unsigned grid_tiles(int tiles_m, int tiles_n, const GemmGroup& g) {
+    if (g.n == 0) return (unsigned)(tiles_m * tiles_n);
+    if (g.role == 2) return (unsigned)(g.n * tiles_m * tiles_n);
+    int tok_tiles = 0;
+    for (int e = 0; e < g.n; ++e) tok_tiles += (g.seg[e + 1] - g.seg[e] + 255) / 256;
+    return (unsigned)(tok_tiles * (g.role == 0 ? tiles_n : tiles_m));
+}
+
 template <bool SPARSE>
 static hipError_t launch_v2(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t Ra,
-                            int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, int blocked, hipStream_t s) {
+                            int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, int blocked, hipStream_t s,
+                            const GemmGroup* grp) {
     const int tiles_m = (int)((Ra + 255) / 256), tiles_n = (int)((Rb + 255) / 256);
-    dim3 grid((unsigned)(tiles_m * tiles_n));
+    const GemmGroup g = grp ? *grp : GemmGroup();
+    if (g.n && (!blocked || g.n > GemmGroup::kMaxExperts || (SPARSE && g.role == 2))) return hipErrorInvalidValue;
+    const unsigned tiles = grid_tiles(tiles_m, tiles_n, g);
+    if (tiles == 0) return hipSuccess;
+    dim3 grid(tiles);
     const VnmEpilogue none;
     if (out_i_contig)
         hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, true, 0>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
-                           out, ldo, tiles_m, tiles_n, blocked, none);
+                           out, ldo, tiles_m, tiles_n, blocked, none, g);
     else
         hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, false, 0>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
-                           out, ldo, tiles_m, tiles_n, blocked, none);
+                           out, ldo, tiles_m, tiles_n, blocked, none, g);
     return hipGetLastError();
 }
 
 hipError_t launch_gemm_nt_v2(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
                              int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
-    if (sparse_a) return launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s);
-    return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s);
+    if (sparse_a) return launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s, nullptr);
+    return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s, nullptr);
 }
 
 hipError_t launch_gemm_nt_blocked(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
-                                  int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
-    if (sparse_a) return launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 1, s);
-    return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 1, s);
+                                  int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s,
+                                  const GemmGroup* grp) {
+    if (sparse_a) return launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 1, s, grp);
+    return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 1, s, grp);
 }
 
 hipError_t launch_gemm_vnm_epilogue(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t F,
-                                    int64_t T, int64_t K, uint16_t* out, const VnmEpilogue& ep, hipStream_t s) {
+                                    int64_t T, int64_t K, uint16_t* out, const VnmEpilogue& ep, hipStream_t s, const GemmGroup* grp) {
     const int tiles_m = (int)((F + 255) / 256), tiles_n = (int)((T + 255) / 256);
-    dim3 grid((unsigned)(tiles_m * tiles_n));
+    const GemmGroup g = grp ? *grp : GemmGroup();
+    if (g.n && (g.n > GemmGroup::kMaxExperts || g.role != 1)) return hipErrorInvalidValue;
+    const unsigned tiles = grid_tiles(tiles_m, tiles_n, g);
+    if (tiles == 0) return hipSuccess;
+    dim3 grid(tiles);
     if (ep.mode == 1)
         hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 1>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
-                           tiles_m, tiles_n, 1, ep);
+                           tiles_m, tiles_n, 1, ep, g);
     else
         hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 2>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
-                           tiles_m, tiles_n, 1, ep);
+                           tiles_m, tiles_n, 1, ep, g);
     return hipGetLastError();
 }
 

@@ -24,6 +24,21 @@ struct VnmEpilogue {
     uint16_t* at = nullptr;
 };
 
+// Grouped (mixture-of-experts) form of a contraction: the token axis is cut into n consecutive segments, one per
+// expert (offsets seg[0] = 0 <= ... <= seg[n] = all tokens, multiples of 64), and each segment meets its own
+// expert's weight operand.  `role` says which axis of the NT contraction the tokens are:
+//   0: the i rows (A is token-indexed, B is the expert's weight matrix, out rows are tokens);
+//   1: the j rows (A is the expert's packed weight matrix, B is token-indexed);
+//   2: the contraction axis (A and B are [., all tokens] matrices, every expert gets its own output).
+// Strides are per expert, in elements of the pointed-to type.  Token-indexed tensors always carry all tokens.
+struct GemmGroup {
+    static constexpr int kMaxExperts = 64;
+    int n = 0;                      // 0: ordinary single contraction
+    int role = 0;
+    int64_t a_stride = 0, m_stride = 0, b_stride = 0, bias_stride = 0, out_stride = 0;
+    int32_t seg[kMaxExperts + 1] = {0};
+};
+
 hipError_t launch_prune24(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
                           uint8_t* meta, hipStream_t stream);
 // v24blk / m24blk (both or neither): also write the result as a plain 2:4 matrix over all F columns in the
@@ -34,14 +49,16 @@ hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uin
                               int64_t T, int64_t F, uint16_t* dvals, uint16_t* v24blk, uint8_t* m24blk, hipStream_t s);
 // 2:4 prune-and-pack for the fused step: canonical outputs plus the blocked copies the GEMMs read;
 // trans = 1 can also emit a blocked copy of the source matrix itself (rows = its rows, K = its columns).
+// batch > 1 (trans = 1 only): `batch` matrices of the same shape, consecutive in every argument.
 hipError_t launch_prune24_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
-                               uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream);
+                               uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream, int batch = 1);
 hipError_t launch_vnm_to_24(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
                             uint16_t* vals24, uint8_t* meta24, hipStream_t s);
 hipError_t launch_vnm_expand_t(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
                                uint16_t* out, int blocked, hipStream_t s);
+// batch > 1: `batch` matrices [R, C] (ld = C) back to back, transposed one by one.
 hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld, uint16_t* out, int blocked, uint16_t* out_same,
-                            hipStream_t s);
+                            hipStream_t s, int batch = 1);
 
 // C[i, j] = sum_k A[i, k] * B[j, k]  (both operands K-contiguous).
 //   sparse_a: A given as 2:4 packed (a_vals [Ra, K/2], a_meta [Ra, K/8]) and multiplied on the
@@ -49,10 +66,13 @@ hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld
 //   out_i_contig: 1 -> out[j * ldo + i] (+ bias[i]);  0 -> out[i * ldo + j].
 //   blocked (launch_gemm_nt_blocked): both operands (and the metadata) are in the blocked layout of common.hpp.
 // eq. (1) / eq. (4) with the fused epilogue above: A packed 2:4 [Ra = F rows], B = [Rb = T rows], all blocked; out [T, F].
+// grp (optional, blocked launchers only): grouped form, see GemmGroup; Ra / Rb / K then count all tokens on the token axis.
 hipError_t launch_gemm_vnm_epilogue(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t F,
-                                    int64_t T, int64_t K, uint16_t* out, const VnmEpilogue& ep, hipStream_t s);
+                                    int64_t T, int64_t K, uint16_t* out, const VnmEpilogue& ep, hipStream_t s,
+                                    const GemmGroup* grp = nullptr);
 hipError_t launch_gemm_nt_blocked(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
-                                  int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
+                                  int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s,
+                                  const GemmGroup* grp = nullptr);
 hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
                           int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
 

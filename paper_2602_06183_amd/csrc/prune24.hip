@@ -51,6 +51,12 @@ __global__ void __launch_bounds__(256) prune24_cols_kernel(const uint16_t* __res
     const int64_t r0 = (int64_t)blockIdx.x * TR;
     const int k0 = blockIdx.y * TK;
     const int tid = threadIdx.x;
+    if (blockIdx.z) {   // batched form: matrix blockIdx.z of a stack of [K, R] sources (ld = R)
+        const int64_t m = (int64_t)blockIdx.z * R * K;
+        src += m; vals += m / 2; meta += m / 8;
+        if (vblk) { vblk += m / 2; mblk += m / 8; }
+        if (src_blk) src_blk += m;
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int kk = tid / 8 + 32 * i, seg = tid % 8;
@@ -140,13 +146,14 @@ hipError_t launch_prune24(const uint16_t* src, int64_t R, int64_t K, int64_t ld,
 }
 
 hipError_t launch_prune24_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
-                               uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream) {
+                               uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream, int batch) {
+    if (batch > 1 && (!trans || ld != R)) return hipErrorInvalidValue;
     if (!trans) {
         dim3 grid((unsigned)((K / 64 + 3) / 4), (unsigned)(R / 16));
         if (mode == 0) hipLaunchKernelGGL((prune24_rows_step_kernel<false>), grid, dim3(256), 0, stream, src, (int)K, ld, vals, meta, vblk, mblk);
         else           hipLaunchKernelGGL((prune24_rows_step_kernel<true>), grid, dim3(256), 0, stream, src, (int)K, ld, vals, meta, vblk, mblk);
     } else {
-        dim3 grid((unsigned)(R / 64), (unsigned)((K + 127) / 128));
+        dim3 grid((unsigned)(R / 64), (unsigned)((K + 127) / 128), (unsigned)batch);
         if (mode == 0) hipLaunchKernelGGL((prune24_cols_kernel<false>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta, vblk, mblk, src_blk);
         else           hipLaunchKernelGGL((prune24_cols_kernel<true>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta, vblk, mblk, src_blk);
     }

@@ -202,6 +202,11 @@ __global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* __r
     __shared__ __attribute__((aligned(16))) uint16_t tile[64][64 + 2];
     const int tid = threadIdx.x;
     const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+    {   // batched form: matrix blockIdx.z of a stack of [R, C] matrices
+        const int64_t m = (int64_t)blockIdx.z * R * C;
+        in += m; out += m;
+        if (out_same) out_same += m;
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int e = tid + 256 * i, rr = e >> 3, seg = e & 7;
@@ -262,8 +267,9 @@ hipError_t launch_vnm_expand_t(const uint16_t* vals, const uint8_t* meta, const 
 }
 
 hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld, uint16_t* out, int blocked, uint16_t* out_same,
-                            hipStream_t s) {
-    dim3 grid((unsigned)(C / 64), (unsigned)(R / 64));
+                            hipStream_t s, int batch) {
+    if (batch > 1 && ld != C) return hipErrorInvalidValue;
+    dim3 grid((unsigned)(C / 64), (unsigned)(R / 64), (unsigned)batch);
     hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, in, R, C, ld, out, blocked, out_same);
     return hipGetLastError();
 }

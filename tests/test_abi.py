@@ -64,6 +64,20 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     bad = binding._Cfg(512, 250, 1024, 64, 8, 0, 0)
     assert lib.ffn_sparse_step(ctypes.byref(bad), *args, fake, 1 << 30, None) == -1
     assert len(lib.sffn_last_error()) > 0
+    # grouped step: the segment table is a host array and is validated before anything is enqueued
+    big = 1 << 40
+    seg = lambda *v: (ctypes.c_int64 * len(v))(*v)
+    assert lib.ffn_sparse_step_grouped(ctypes.byref(cfg), 2, None, *args, fake, big, None) == -1
+    assert lib.ffn_sparse_step_grouped(ctypes.byref(cfg), 0, seg(0), *args, fake, big, None) == -1
+    assert lib.ffn_sparse_step_grouped(ctypes.byref(cfg), 65, seg(*([0] * 66)), *args, fake, big, None) == -1
+    assert lib.ffn_sparse_step_grouped(ctypes.byref(cfg), 2, seg(0, 100, 512), *args, fake, big, None) == -1     # not a multiple of 64
+    assert lib.ffn_sparse_step_grouped(ctypes.byref(cfg), 2, seg(0, 320, 448), *args, fake, big, None) == -1     # does not end at T
+    assert lib.ffn_sparse_step_grouped(ctypes.byref(cfg), 2, seg(64, 320, 512), *args, fake, big, None) == -1    # does not start at 0
+    assert lib.ffn_sparse_step_grouped(ctypes.byref(cfg), 3, seg(0, 320, 256, 512), *args, fake, big, None) == -1  # descending
+    assert lib.ffn_sparse_step_grouped(ctypes.byref(cfg), 2, seg(0, 320, 512), *args, fake, 16, None) == -3
+    assert lib.sffn_grouped_workspace_bytes(ctypes.byref(cfg), 1) == lib.sffn_workspace_bytes(ctypes.byref(cfg))
+    assert lib.sffn_grouped_workspace_bytes(ctypes.byref(cfg), 4) > lib.sffn_workspace_bytes(ctypes.byref(cfg))
+    assert lib.sffn_grouped_workspace_bytes(ctypes.byref(cfg), 0) == 0
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

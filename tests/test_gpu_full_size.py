@@ -9,7 +9,7 @@ import torch
 import oracle
 import paper_2602_06183_amd as sffn
 from tests.util import to_dev, to_bits, assert_gemm_close
-from workload import CONFIGS, make_ffn_inputs
+from workload import CONFIGS, make_ffn_inputs, make_moe_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -21,27 +21,35 @@ def _run(dev, T, D, F, keep):
     return step, outs
 
 
+PACKED_KEYS = ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta", "y2_vals", "y2_meta", "colidx", "dy1_vals", "y1_kept")
+
+
 @pytest.mark.parametrize("name,tb_slices", [("1b", None), ("7b", [(0, 2), (101, 103)]), ("70b", [(0, 1), (77, 78)]),
                                             ("moe_expert", [(0, 1), (30, 31)])])
 def test_full_size_step(name, tb_slices):
     T, D, F = CONFIGS[name]
     inp = make_ffn_inputs(T, D, F, seed=0)
     dev = {k: to_dev(v) for k, v in inp.items()}
-    packed_keys = ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta", "y2_vals", "y2_meta", "colidx", "dy1_vals", "y1_kept")
 
     step0, outs0 = _run(dev, T, D, F, keep=False)              # what bench.py times
-    fast = [to_bits(t).copy() for t in outs0] + [to_bits(step0.saved()[k]).copy() for k in packed_keys]
+    fast = [to_bits(t).copy() for t in outs0] + [to_bits(step0.saved()[k]).copy() for k in PACKED_KEYS]
     del step0, outs0
     torch.cuda.empty_cache()
     step, outs = _run(dev, T, D, F, keep=True)
     sv = step.saved()
-    full = [to_bits(t) for t in outs] + [to_bits(sv[k]) for k in packed_keys]
+    full = [to_bits(t) for t in outs] + [to_bits(sv[k]) for k in PACKED_KEYS]
     for a, b in zip(fast, full):
         assert np.array_equal(a, b)
     del fast
+    _sampled_step_check(inp, full, to_bits(sv["y1"]), to_bits(sv["dy2"]), tb_slices)
+
+
+def _sampled_step_check(inp, full, y1, dy2, tb_slices):
+    """inp: X, W1, W2, b1, dY of ONE FFN; full: its Y3, dX, dW1, dW2 followed by the PACKED_KEYS tensors."""
+    T, D = inp["X"].shape
+    F = inp["W1"].shape[0]
     Y3, dX, dW1, dW2 = full[:4]
     w1v, w1m, w2v, w2m, yv, ym, yc, dv, _ = full[4:]
-    y1, dy2 = to_bits(sv["y1"]), to_bits(sv["dy2"])
     rng = np.random.default_rng(123)
 
     # 2:4 weights: bit-exact, everywhere at 1b, on two bands of 1024 rows at the larger shapes (rows are independent)
@@ -100,3 +108,46 @@ def test_full_size_step(name, tb_slices):
     a = oracle.bits_to_f64(dense_cols(dv))
     ref = oracle.f64_to_bits(a.T @ oracle.bits_to_f64(inp["X"]))
     assert_gemm_close(dW1[cols], ref, "dW1 rows")
+
+
+def test_full_size_grouped_step():
+    """configs[4]: 8 experts of d_model 4096, d_ff 14336, 16384 tokens routed top-2 (uneven 64-row-aligned segments),
+    one grouped launch per stage.  The timed configuration (no dense y1 / dy2) must agree bit for bit with the
+    one that stores them; two experts are then checked like a full-size plain step, the others on their 2:4 weights."""
+    D, F, E = 4096, 14336, 8
+    m = make_moe_inputs(n_tokens=16384, n_experts=E, top_k=2, D=D, F=F, seed=0)
+    seg = m["seg"]
+    dev = {k: to_dev(m[k]) for k in ("X", "W1", "W2", "b1", "dY")}
+
+    def run(keep):
+        step = sffn.FfnStepGrouped(seg, D, F, sffn.MODE_HARD, keep_dense=keep)
+        outs = step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+        torch.cuda.synchronize()
+        return step, outs
+
+    step0, outs0 = run(False)
+    fast = [to_bits(t).copy() for t in outs0] + [to_bits(step0.saved()[k]).copy() for k in PACKED_KEYS]
+    del step0, outs0
+    torch.cuda.empty_cache()
+    step, outs = run(True)
+    sv = step.saved()
+    full = [to_bits(t) for t in outs] + [to_bits(sv[k]) for k in PACKED_KEYS]
+    for a, b in zip(fast, full):
+        assert np.array_equal(a, b)
+    del fast
+    y1, dy2 = to_bits(sv["y1"]), to_bits(sv["dy2"])
+    for e in range(E):
+        a, b = int(seg[e]), int(seg[e + 1])
+        if e in (1, 6):
+            inp = dict(X=m["X"][a:b], W1=m["W1"][e], W2=m["W2"][e], b1=m["b1"][e], dY=m["dY"][a:b])
+            Y3, dX, dW1, dW2 = full[:4]
+            w1v, w1m, w2v, w2m, yv, ym, yc, dv, yk = full[4:]
+            part = [Y3[a:b], dX[a:b], dW1[e], dW2[e], w1v[e], w1m[e], w2v[e], w2m[e], yv[a:b], ym[a:b], yc[a // 64:b // 64], dv[a:b], None]
+            nb = (b - a) // 64
+            _sampled_step_check(inp, part, y1[a:b], dy2[a:b], [(0, 1), (nb - 1, nb)])      # the last block holds the zero padding
+        else:
+            r = slice(F - 512, F)
+            rv, rm = oracle.prune24_compress(m["W1"][e][r])
+            assert np.array_equal(full[4][e][r], rv) and np.array_equal(full[5][e][r], rm)
+            rv, rm = oracle.prune24_compress(np.ascontiguousarray(m["W2"][e][:, r].T))
+            assert np.array_equal(full[6][e][r], rv) and np.array_equal(full[7][e][r], rm)

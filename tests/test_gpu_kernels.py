@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2602_06183_amd as sffn
 from tests.util import to_dev, to_bits, assert_gemm_close
-from workload import make_ffn_inputs, bf16_bits_from_f32
+from workload import make_ffn_inputs, make_moe_inputs, bf16_bits_from_f32
 
 pytestmark = pytest.mark.gpu
 
@@ -153,13 +153,10 @@ def test_gemm_exact_on_small_integers():
         assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.vnm_wgrad(av, am, ac, G, fmaj)))
 
 
-def _teacher_forced_step_check(T, D, F, mode, seed):
-    inp = make_ffn_inputs(T, D, F, seed=seed)
-    dev = {k: to_dev(v) for k, v in inp.items()}
-    (Y3, dX, dW1, dW2), step = sffn.ffn_sparse_step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"], mode)
-    torch.cuda.synchronize()
-    s = {k: to_bits(v) for k, v in step.saved().items()}
-    # each oracle stage consumes the GPU's output of the stage before it
+def _check_step_against_oracle(inp, s, outs, mode):
+    """Teacher-forced parity of one FFN step: each oracle stage consumes the GPU's output of the stage before it.
+    inp: X, W1, W2, b1, dY; s: the tensors the step saved; outs: Y3, dX, dW1, dW2 (all numpy bit patterns)."""
+    T, F = s["y1"].shape
     rv, rm = oracle.prune24_compress(inp["W1"], mode)
     assert np.array_equal(s["w1_vals"], rv) and np.array_equal(s["w1_meta"], rm)
     assert_gemm_close(s["y1"], oracle.spmm24(inp["X"], s["w1_vals"], s["w1_meta"], inp["b1"]), "y1")
@@ -175,16 +172,26 @@ def _teacher_forced_step_check(T, D, F, mode, seed):
     want_kept[slot_of[tt, ff] - 1] = s["y1"][tt, ff]
     want_kept = want_kept.reshape(T // 64, 64, F // 64, 8, 2).transpose(0, 2, 1, 3, 4)       # [tb, fb, t, blk, 2]
     assert np.array_equal(s["y1_kept"].reshape(-1), want_kept.reshape(-1))
-    assert_gemm_close(to_bits(Y3), oracle.vnm_spmm(yv, ym, yc, inp["W2"], 0), "y3")
+    assert_gemm_close(outs["Y3"], oracle.vnm_spmm(yv, ym, yc, inp["W2"], 0), "y3")
     rv2, rm2 = oracle.prune24_compress(np.ascontiguousarray(inp["W2"].T), mode)
     assert np.array_equal(s["w2t_vals"], rv2) and np.array_equal(s["w2t_meta"], rm2)
     assert_gemm_close(s["dy2"], oracle.spmm24(inp["dY"], rv2, rm2, None), "dy2")
     dv = oracle.dsqrelu_vnm(s["dy2"], s["y1"], ym, yc)
     assert np.array_equal(s["dy1_vals"], dv)
-    assert_gemm_close(to_bits(dW2), oracle.vnm_wgrad(yv, ym, yc, inp["dY"], 0), "dW2")
-    assert_gemm_close(to_bits(dX), oracle.vnm_spmm(dv, ym, yc, inp["W1"], 1), "dX")
-    assert_gemm_close(to_bits(dW1), oracle.vnm_wgrad(dv, ym, yc, inp["X"], 1), "dW1")
-    return inp, s, dict(Y3=to_bits(Y3), dX=to_bits(dX), dW1=to_bits(dW1), dW2=to_bits(dW2))
+    assert_gemm_close(outs["dW2"], oracle.vnm_wgrad(yv, ym, yc, inp["dY"], 0), "dW2")
+    assert_gemm_close(outs["dX"], oracle.vnm_spmm(dv, ym, yc, inp["W1"], 1), "dX")
+    assert_gemm_close(outs["dW1"], oracle.vnm_wgrad(dv, ym, yc, inp["X"], 1), "dW1")
+
+
+def _teacher_forced_step_check(T, D, F, mode, seed):
+    inp = make_ffn_inputs(T, D, F, seed=seed)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    (Y3, dX, dW1, dW2), step = sffn.ffn_sparse_step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"], mode)
+    torch.cuda.synchronize()
+    s = {k: to_bits(v) for k, v in step.saved().items()}
+    outs = dict(Y3=to_bits(Y3), dX=to_bits(dX), dW1=to_bits(dW1), dW2=to_bits(dW2))
+    _check_step_against_oracle(inp, s, outs, mode)
+    return inp, s, outs
 
 
 @pytest.mark.parametrize("mode", [sffn.MODE_HARD, sffn.MODE_SOFT])
@@ -232,3 +239,64 @@ def test_step_is_deterministic_and_reusable():
     b = [to_bits(t).copy() for t in step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
     for x, y in zip(a, b):
         assert np.array_equal(x, y)
+
+
+def _expert_view(m, s, outs, seg, e):
+    """Expert e's share of a grouped step: its inputs, saved tensors and outputs."""
+    a, b = int(seg[e]), int(seg[e + 1])
+    F = s["y1"].shape[1]
+    inp = dict(X=m["X"][a:b], W1=m["W1"][e], W2=m["W2"][e], b1=m["b1"][e], dY=m["dY"][a:b])
+    se = {k: s[k][e] for k in ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta")}
+    se.update({k: s[k][a:b] for k in ("y1", "y2_vals", "y2_meta", "dy2", "dy1_vals")})
+    se["colidx"] = s["colidx"][a // 64:b // 64]
+    se["y1_kept"] = s["y1_kept"].reshape(-1)[a * F // 4:b * F // 4]
+    oe = dict(Y3=outs["Y3"][a:b], dX=outs["dX"][a:b], dW1=outs["dW1"][e], dW2=outs["dW2"][e])
+    return inp, se, oe
+
+
+def _run_grouped(m, D, F, mode, keep_dense=True):
+    dev = {k: to_dev(m[k]) for k in ("X", "W1", "W2", "b1", "dY")}
+    step = sffn.FfnStepGrouped(m["seg"], D, F, mode, keep_dense=keep_dense)
+    Y3, dX, dW1, dW2 = step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    torch.cuda.synchronize()
+    s = {k: to_bits(v).copy() for k, v in step.saved().items()}
+    return s, dict(Y3=to_bits(Y3).copy(), dX=to_bits(dX).copy(), dW1=to_bits(dW1).copy(), dW2=to_bits(dW2).copy())
+
+
+@pytest.mark.parametrize("mode", [sffn.MODE_HARD, sffn.MODE_SOFT])
+def test_grouped_step_matches_oracle_per_expert(mode):
+    """Mixture-of-experts form, uneven segments from the routing seed (several 256-token tiles plus ragged tails):
+    every expert's share is checked teacher-forced like the plain step."""
+    D, F = 192, 320
+    m = make_moe_inputs(n_tokens=900, n_experts=4, top_k=2, D=D, F=F, seed=2)
+    assert len(set(np.diff(m["seg"]).tolist())) > 1
+    s, outs = _run_grouped(m, D, F, mode)
+    for e in range(4):
+        inp, se, oe = _expert_view(m, s, outs, m["seg"], e)
+        _check_step_against_oracle(inp, se, oe, mode)
+
+
+def test_grouped_step_empty_and_single_block_experts():
+    """Segments of 0, 64 and 576 rows: the empty expert gets zero weight gradients, the others match the
+    plain step on their rows bit for bit (same kernels, same accumulation order)."""
+    D, F = 128, 256
+    seg = np.array([0, 0, 64, 640, 640], dtype=np.int64)
+    parts = [make_ffn_inputs(int(seg[e + 1] - seg[e]), D, F, seed=10 + e) if seg[e + 1] > seg[e] else make_ffn_inputs(64, D, F, seed=10 + e)
+             for e in range(4)]
+    m = dict(X=np.concatenate([parts[1]["X"], parts[2]["X"]]), dY=np.concatenate([parts[1]["dY"], parts[2]["dY"]]),
+             W1=np.stack([p["W1"] for p in parts]), W2=np.stack([p["W2"] for p in parts]), b1=np.stack([p["b1"] for p in parts]), seg=seg)
+    s, outs = _run_grouped(m, D, F, sffn.MODE_HARD)
+    for e in (0, 3):
+        assert not outs["dW1"][e].any() and not outs["dW2"][e].any()
+        rv, rm = oracle.prune24_compress(m["W1"][e])
+        assert np.array_equal(s["w1_vals"][e], rv) and np.array_equal(s["w1_meta"][e], rm)
+    for e in (1, 2):
+        inp, se, oe = _expert_view(m, s, outs, seg, e)
+        _check_step_against_oracle(inp, se, oe, sffn.MODE_HARD)
+        dev = {k: to_dev(v) for k, v in inp.items()}
+        (Y3, dX, dW1, dW2), step = sffn.ffn_sparse_step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"], sffn.MODE_HARD)
+        for k, t in (("Y3", Y3), ("dX", dX), ("dW1", dW1), ("dW2", dW2)):
+            assert np.array_equal(oe[k], to_bits(t)), k
+        sv = step.saved()
+        for k in ("y2_vals", "y2_meta", "colidx", "dy1_vals", "y1"):
+            assert np.array_equal(se[k], to_bits(sv[k])), k

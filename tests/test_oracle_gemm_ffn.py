@@ -157,3 +157,31 @@ def test_workload_zero_fraction_and_moe_segments():
     counts, offs = make_moe_segments()
     assert counts.sum() == 16384 * 2 and np.all(offs % 64 == 0) and np.all(np.diff(offs) >= counts)
     assert len(set(counts.tolist())) > 1
+
+
+def test_grouped_step_is_the_plain_step_per_segment_and_ignores_zero_padding():
+    """Mixture-of-experts form: one expert over all rows is the plain step; rows of zeros appended to a
+    segment (the 64-row padding) change nothing the expert returns for its real rows or its weights:
+    a zero row gives y1 = b1 < 0, so y2 = 0 there, which adds nothing to the column scores, and its
+    dY row is zero, which adds nothing to either weight gradient."""
+    from workload import make_moe_inputs
+    m = make_moe_inputs(n_tokens=150, n_experts=3, top_k=2, D=64, F=128, seed=5)
+    seg, counts = m["seg"], m["counts"]
+    assert int(counts.sum()) == 300 and all(int(v) % 64 == 0 for v in seg) and int(seg[-1]) >= 300
+    res = oracle.ffn_sparse_step_grouped_ref(m["X"], m["W1"], m["W2"], m["b1"], m["dY"], seg)
+    for e in range(3):
+        a, n = int(seg[e]), int(counts[e])
+        assert n % 64 != 0                                   # the case is only a test if there is padding
+        assert not m["X"][a + n:int(seg[e + 1])].any() and not m["dY"][a + n:int(seg[e + 1])].any()
+        r = res[e]
+        # weight gradients recomputed from the real rows alone, as dense fp64 sums over the masked activations
+        y2d = oracle.bits_to_f64(oracle.vnm_decompress(r["y2_vals"], r["y2_meta"], r["colidx"]))
+        dy1d = oracle.bits_to_f64(oracle.vnm_decompress(r["dy1_vals"], r["y2_meta"], r["colidx"]))
+        assert not y2d[n:].any() and not dy1d[n:].any()      # padded rows carry no activation and no gradient
+        assert np.array_equal(r["dW2"], oracle.f64_to_bits(oracle.bits_to_f64(m["dY"][a:a + n]).T @ y2d[:n]))
+        assert np.array_equal(r["dW1"], oracle.f64_to_bits(dy1d[:n].T @ oracle.bits_to_f64(m["X"][a:a + n])))
+    one = oracle.ffn_sparse_step_grouped_ref(m["X"], m["W1"][:1], m["W2"][:1], m["b1"][:1], m["dY"], [0, int(seg[-1])])
+    ref = oracle.ffn_sparse_step_ref(m["X"], m["W1"][0], m["W2"][0], m["b1"][0], m["dY"])
+    for k in ref:
+        assert np.array_equal(one[0][k], ref[k]), k
+    assert oracle.ffn_sparse_step_grouped_ref(m["X"], m["W1"], m["W2"], m["b1"], m["dY"], [0, 0, 64, int(seg[-1])])[0] is None

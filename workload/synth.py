@@ -56,3 +56,24 @@ def make_moe_segments(n_tokens=16384, n_experts=8, top_k=2, seed=0, align=64):
     padded = (counts + align - 1) // align * align
     offsets = np.concatenate([[0], np.cumsum(padded)]).astype(np.int64)
     return counts, offsets
+
+
+def make_moe_inputs(n_tokens, n_experts, top_k, D, F, seed=0, zero_fraction=0.90, w_std=0.02, align=64):
+    """Grouped-FFN workload: `n_tokens` tokens routed top-k over `n_experts` experts by N(0,1) logits (uneven
+    counts from the seed).  Each expert's slots are consecutive rows, padded with zero rows to a multiple of
+    `align`; expert e's weights and bias come from make_ffn_inputs' recipe with seed + e, its rows from a
+    generator of their own.  Returns X, dY [T, D], W1 [E, F, D], W2 [E, D, F], b1 [E, F], counts, seg (offsets)."""
+    counts, seg = make_moe_segments(n_tokens, n_experts, top_k, seed, align)
+    T = int(seg[-1])
+    X = np.zeros((T, D), dtype=np.uint16)
+    dY = np.zeros((T, D), dtype=np.uint16)
+    W1 = np.empty((n_experts, F, D), dtype=np.uint16)
+    W2 = np.empty((n_experts, D, F), dtype=np.uint16)
+    b1 = np.empty((n_experts, F), dtype=np.float32)
+    for e in range(n_experts):
+        part = make_ffn_inputs(int(counts[e]), D, F, seed + e, zero_fraction, w_std)
+        a = int(seg[e])
+        X[a:a + int(counts[e])] = part["X"]
+        dY[a:a + int(counts[e])] = part["dY"]
+        W1[e], W2[e], b1[e] = part["W1"], part["W2"], part["b1"]
+    return dict(X=X, W1=W1, W2=W2, b1=b1, dY=dY, counts=counts, seg=seg)
