@@ -122,7 +122,7 @@ int sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, int V, int M, 
     REQUIRE(aligned16(y1) && aligned16(vals) && aligned16(meta) && aligned16(colidx), SFFN_EINVAL,
             "sqrelu_vnm_compress: pointers must be 16-byte aligned");
     REQUIRE(fits_int(T) && fits_int(F) && T / 64 < 65536, SFFN_EUNSUPPORTED, "sqrelu_vnm_compress: T too large");
-    LAUNCH(launch_sqrelu_vnm_compress(y1, T, F, vals, meta, colidx, nullptr, nullptr, (hipStream_t)stream), "sqrelu_vnm_compress");
+    LAUNCH(launch_sqrelu_vnm_compress(y1, T, F, vals, meta, colidx, (hipStream_t)stream), "sqrelu_vnm_compress");
     return SFFN_OK;
 }
 
@@ -184,7 +184,7 @@ int dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, co
     REQUIRE(aligned16(dy2) && aligned16(y1) && aligned16(meta) && aligned16(colidx) && aligned16(dvals), SFFN_EINVAL,
             "dsqrelu_vnm: pointers must be 16-byte aligned");
     REQUIRE(fits_int(T) && fits_int(F) && T < 65536, SFFN_EUNSUPPORTED, "dsqrelu_vnm: T must be below 65536");
-    LAUNCH(launch_dsqrelu_vnm(dy2, y1, meta, colidx, T, F, dvals, nullptr, nullptr, (hipStream_t)stream), "dsqrelu_vnm");
+    LAUNCH(launch_dsqrelu_vnm(dy2, y1, meta, colidx, T, F, dvals, (hipStream_t)stream), "dsqrelu_vnm");
     return SFFN_OK;
 }
 

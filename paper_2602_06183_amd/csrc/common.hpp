@@ -51,10 +51,14 @@ __device__ __forceinline__ uint32_t select24(uint32_t a0, uint32_t a1, uint32_t 
 __host__ __device__ __forceinline__ int64_t blk_off(int64_t r, int64_t k, int64_t KC) {
     return (((r >> 4) * KC + (k >> 5)) << 9) + ((r & 15) << 5) + (k & 31);
 }
-// Metadata of a 2:4 matrix in blocks of 64 rows x 8 bytes (one main-loop step of 64 k): byte address of
-// the metadata byte covering k..k+7 of row r, with KS = K / 64.
+// Metadata of a 2:4 matrix, blocked for the sparse matrix instruction: one 256-byte unit per (32 rows, 64 k).
+// v_smfmac_f32_32x32x32_bf16 wants, in lane (row % 32) + 32 * h, the sixteen index bits of the row's survivors
+// in k 16h..16h+15 of a 32-k step; a unit stores, for each such lane, the two 32-k steps s = 0, 1 of its 64 k as
+// one 32-bit word (low half: s = 0) at byte 128 h + 4 (row % 32).  A wavefront therefore fetches a unit with one
+// 4-byte-per-lane LDS-DMA load, reads it back with one conflict-free ds_read_b32 and picks the step through the
+// instruction's ABID field.  mblk_off = byte address of the metadata byte covering k..k+7 of row r, KS = K / 64.
 __host__ __device__ __forceinline__ int64_t mblk_off(int64_t r, int64_t k, int64_t KS) {
-    return (((r >> 6) * KS + (k >> 6)) << 9) + ((r & 63) << 3) + ((k & 63) >> 3);
+    return (((r >> 5) * KS + (k >> 6)) << 8) + (((k >> 4) & 1) << 7) + ((r & 31) << 2) + (((k >> 5) & 1) << 1) + ((k >> 3) & 1);
 }
 
 // Two survivors per 8 columns leave at most two per aligned group of four, so a V:2:8 row block is

@@ -80,12 +80,13 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <bool SPARSE, bool OUT_I_CONTIG, int EPI>
+template <bool SPARSE, bool OUT_I_CONTIG, int EPI, bool BLOCKED>
 __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restrict__ a_vals, const uint8_t* __restrict__ a_meta,
                                                         const uint16_t* __restrict__ B, const float* __restrict__ bias,
                                                         int Ra, int Rb, int K, uint16_t* __restrict__ out, int64_t ldo,
-                                                        int tiles_m, int tiles_n, int blocked, VnmEpilogue ep, GemmGroup grp) {
-    static_assert(EPI == 0 || (SPARSE && OUT_I_CONTIG), "the V:N:M epilogues belong to the 2:4-weight GEMMs");
+                                                        int tiles_m, int tiles_n, VnmEpilogue ep, GemmGroup grp) {
+    static_assert(EPI == 0 || (SPARSE && OUT_I_CONTIG && BLOCKED), "the V:N:M epilogues belong to the 2:4-weight GEMMs of the fused step");
+    constexpr bool blocked = BLOCKED;       // operands in the blocked layout of common.hpp (fused step) or row-major (stand-alone entry points)
     using C = Cfg<SPARSE>;
     constexpr int BM = C::BM, BN = C::BN, WM = 128, WN = 64, FM = 4, FN = 2;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[C::NSTAGE * C::STAGE];
@@ -170,14 +171,16 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         }
         a_lane = blocked ? (rb * 32 + c * 8) * 2 : (uint32_t)(rb * lda + c * 8) * 2;
         b_lane = blocked ? (rb * 32 + c * 8) * 2 : (uint32_t)(rb * Kld + c * 8) * 2;
+        // metadata: one 4-byte-per-lane load brings 32 rows x 64 k; blocked: one unit of common.hpp, lane-linear;
+        // row-major: lane -> (row lane / 2, 4-byte half lane % 2), landing as [row][8 bytes]
         m_lane = blocked ? lane * 4 : (uint32_t)((lane >> 1) * (Kld / 8) + (lane & 1) * 4);
         if (SPARSE) {
             int gr = i0 + wave * 32; gr = gr < Ra ? gr : Ra - 32;
-            m_base = uniform64(blocked ? a_meta + (((int64_t)(gr >> 6) * (Kld / 64) + k_base / 64) << 9) + (gr & 63) * 8 : a_meta + (int64_t)gr * (Kld / 8));
+            m_base = uniform64(blocked ? a_meta + (((int64_t)(gr >> 5) * (Kld / 64) + k_base / 64) << 8) : a_meta + (int64_t)gr * (Kld / 8));
         }
         a_kstep = blocked ? 1024 : 64;
         b_kstep = blocked ? 1024 * (C::BK / 32) : C::BK * 2;
-        m_kstep = blocked ? 512 : 8;
+        m_kstep = blocked ? 256 : 8;
     }
     // the DMA loads of one stage, issued in two halves (h = 0, 1) so that they can sit between matrix instructions
     auto issue_half = [&](int kt, int stage, int h) {
@@ -203,7 +206,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     for (int a = 0; a < FM; ++a) {
         const int row = wm * WM + a * 32 + l32;
         a_off[a] = row * 64 + ((lh ^ ((row >> 2) & 3)) << 4);
-        m_off[a] = C::A_BYTES + C::B_BYTES + row * 8 + 2 * lh;
+        // blocked: the lane's word of unit row / 32 holds both 32-k steps (picked by ABID); row-major: [row][8 bytes]
+        m_off[a] = C::A_BYTES + C::B_BYTES + (blocked ? (row >> 5) * 256 + lane * 4 : row * 8 + 2 * lh);
     }
 #pragma unroll
     for (int b = 0; b < FN; ++b) {
@@ -227,9 +231,14 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         Frag16 b16[FN];     // SPARSE: 16 k-values per lane
         Frag8 b8[FN];       // dense: 8 k-values per lane
     };
-    auto read_a = [&](FragSet& f, const unsigned char* st, int ks, int a) {
+    // `prev` = the set that holds the first 32-k step of the same tile (its index word serves both steps)
+    auto read_a = [&](FragSet& f, const FragSet& prev, const unsigned char* st, int ks, int a) {
         f.a[a].u = *reinterpret_cast<const uint4*>(st + (a_off[a] ^ (32 * ks)));
-        if (SPARSE) f.idx[a] = *reinterpret_cast<const uint16_t*>(st + m_off[a] + 4 * ks);
+        if (SPARSE) {
+            if (!blocked) f.idx[a] = *reinterpret_cast<const uint16_t*>(st + m_off[a] + 4 * ks);
+            else if (ks == 0) f.idx[a] = *reinterpret_cast<const uint32_t*>(st + m_off[a]);
+            else f.idx[a] = prev.idx[a];
+        }
     };
     auto read_b = [&](FragSet& f, const unsigned char* st, int ks, int b) {
         if (SPARSE) {
@@ -242,58 +251,61 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     auto read_frags = [&](FragSet& f, int stage, int ks) {
         const unsigned char* st = smem + stage * C::STAGE;
 #pragma unroll
-        for (int a = 0; a < FM; ++a) read_a(f, st, ks, a);
+        for (int a = 0; a < FM; ++a) read_a(f, f, st, ks, a);
 #pragma unroll
         for (int b = 0; b < FN; ++b) read_b(f, st, ks, b);
     };
-    auto mma_row = [&](const FragSet& f, int a) {
+    // second = the set holds the second 32-k step of its tile: blocked metadata then sits in the high half of the index word
+    auto mma_row = [&](const FragSet& f, int a, bool second) {
 #pragma unroll
         for (int b = 0; b < FN; ++b) {
-            if (SPARSE) acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[a].v, f.b16[b].v, acc[a][b], f.idx[a], 0, 0);
-            else        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a].v, f.b8[b].v, acc[a][b], 0, 0, 0);
+            if (!SPARSE)                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a].v, f.b8[b].v, acc[a][b], 0, 0, 0);
+            else if (blocked && second) acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[a].v, f.b16[b].v, acc[a][b], f.idx[a], 0, 1);
+            else                        acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[a].v, f.b16[b].v, acc[a][b], f.idx[a], 0, 0);
         }
     };
 #define SB() __builtin_amdgcn_sched_barrier(0)
 
     const int nk = K / C::BK;            // 0 for an expert without tokens (weight gradients): the output is zeros
-    constexpr int DIST = C::NSTAGE - 1;
     if (nk > 0) {
+    // The ring holds NSTAGE tiles: the one being multiplied, the next one (landed by the middle of the step,
+    // when its first fragments are read) and NSTAGE - 2 in flight.  A stage is refilled right after the
+    // barrier that ends its last fragment reads, so a tile has almost NSTAGE - 1 steps to arrive.
 #pragma unroll
-    for (int p = 0; p < DIST; ++p) issue(p < nk ? p : nk - 1, p);
-    wait_vmcnt<(DIST - 1) * C::LOADS>();
+    for (int p = 0; p < C::NSTAGE; ++p) issue(p < nk ? p : nk - 1, p);
+    wait_vmcnt<(C::NSTAGE - 1) * C::LOADS>();
     __syncthreads();
     FragSet P, Q;
     read_frags(P, 0, 0);
-    int stage = 0, fill = DIST;
+    int stage = 0;
     // One step = two halves of eight matrix instructions.  Each pair of matrix instructions (64+ cycles of
     // the matrix pipe) is followed in program order by a few LDS reads for the other fragment set or by
-    // half of the next stage's DMA issue, so the non-matrix work of a wave hides behind its own MFMAs.
+    // half of a stage's DMA issue, so the non-matrix work of a wave hides behind its own MFMAs.
     for (int kt = 0; kt < nk; ++kt) {
-        const int nxt = (kt + DIST < nk) ? kt + DIST : nk - 1;
+        const int nxt = (kt + C::NSTAGE < nk) ? kt + C::NSTAGE : nk - 1;
         const int next_stage = (stage + 1 == C::NSTAGE) ? 0 : stage + 1;
         const unsigned char* st = smem + stage * C::STAGE;
         const unsigned char* sn = smem + next_stage * C::STAGE;
-        mma_row(P, 0); SB();
-        read_a(Q, st, 1, 0); read_a(Q, st, 1, 1); read_b(Q, st, 1, 0); SB();
-        mma_row(P, 1); SB();
-        read_a(Q, st, 1, 2); read_a(Q, st, 1, 3); read_b(Q, st, 1, 1); SB();
-        mma_row(P, 2); SB();
-        issue_half(nxt, fill, 0); SB();                  // the stage being refilled held tile kt-1
-        mma_row(P, 3); SB();
-        issue_half(nxt, fill, 1); SB();
-        // Q has arrived, tile kt+1 has landed (this wave's part); after the barrier every wave is done
-        // reading this stage and every wave's part of tile kt+1 is in LDS
-        __builtin_amdgcn_s_waitcnt(((DIST - 1) * C::LOADS & 0xF) | ((((DIST - 1) * C::LOADS) >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
+        mma_row(P, 0, false); SB();
+        read_a(Q, P, st, 1, 0); read_a(Q, P, st, 1, 1); read_b(Q, st, 1, 0); SB();
+        mma_row(P, 1, false); SB();
+        read_a(Q, P, st, 1, 2); read_a(Q, P, st, 1, 3); read_b(Q, st, 1, 1); SB();
+        mma_row(P, 2, false); SB();
+        mma_row(P, 3, false); SB();
+        // Q has arrived and tile kt+1 has landed (this wave's part); after the barrier every wave is done
+        // reading this stage, which is refilled at once, and every wave's part of tile kt+1 is in LDS
+        __builtin_amdgcn_s_waitcnt(((C::NSTAGE - 2) * C::LOADS & 0xF) | ((((C::NSTAGE - 2) * C::LOADS) >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
         __builtin_amdgcn_s_barrier();
         SB();
-        mma_row(Q, 0); SB();
-        read_a(P, sn, 0, 0); read_a(P, sn, 0, 1); read_b(P, sn, 0, 0); SB();
-        mma_row(Q, 1); SB();
-        read_a(P, sn, 0, 2); read_a(P, sn, 0, 3); read_b(P, sn, 0, 1); SB();
-        mma_row(Q, 2); SB();
-        mma_row(Q, 3); SB();
+        mma_row(Q, 0, true); SB();
+        issue_half(nxt, stage, 0); SB();
+        read_a(P, P, sn, 0, 0); read_a(P, P, sn, 0, 1); read_b(P, sn, 0, 0); SB();
+        mma_row(Q, 1, true); SB();
+        issue_half(nxt, stage, 1); SB();
+        read_a(P, P, sn, 0, 2); read_a(P, P, sn, 0, 3); read_b(P, sn, 0, 1); SB();
+        mma_row(Q, 2, true); SB();
+        mma_row(Q, 3, true); SB();
         stage = next_stage;
-        fill = (fill + 1 == C::NSTAGE) ? 0 : fill + 1;
     }
 #undef SB
     wait_vmcnt<0>();
@@ -421,10 +433,9 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         // the same block as two plain 2:4 groups (blocked operand of eq. (3) / eq. (7))
                         uint32_t a24, b24, mb8;
                         vnm_block_to_24(v, nib, cw, a24, b24, mb8);
-                        uint32_t m4 = mb8 | (row_shl<1>(mb8) << 8);
-                        m4 |= row_shl<2>(m4) << 16;
+                        const uint32_t m2 = mb8 | (row_shl<1>(mb8) << 8);     // two column blocks = 16 k = one lane's half-word of a unit
                         *reinterpret_cast<uint2*>(v24_p + (int64_t)(it >> 1) * (F / 64) * 512 + (it & 1) * 256) = make_uint2(a24, b24);
-                        if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(m24_p + it * 64) = m4;
+                        if ((lane & 1) == 0) *reinterpret_cast<uint16_t*>(m24_p + (int64_t)(it >> 2) * (F / 64) * 256 + (it & 3) * 32) = (uint16_t)m2;
                         // dense transposed tile for the weight-gradient GEMM: row = hidden unit, column = token
                         const uint32_t o0 = (cw >> (8 * (nib & 3u))) & 0xFFu, o1 = (cw >> (8 * (nib >> 2))) & 0xFFu;
                         *reinterpret_cast<uint16_t*>(ttile + (bl * 8 + o0) * EP + t * 2) = (uint16_t)(v & 0xFFFFu);
@@ -487,12 +498,11 @@ static hipError_t launch_v2(const uint16_t* a_vals, const uint8_t* a_meta, const
     if (tiles == 0) return hipSuccess;
     dim3 grid(tiles);
     const VnmEpilogue none;
-    if (out_i_contig)
-        hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, true, 0>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
-                           out, ldo, tiles_m, tiles_n, blocked, none, g);
-    else
-        hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, false, 0>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)Ra, (int)Rb, (int)K,
-                           out, ldo, tiles_m, tiles_n, blocked, none, g);
+#define SFFN_LAUNCH(ICONTIG, BLK) hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, ICONTIG, 0, BLK>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, \
+                                                   (int)Ra, (int)Rb, (int)K, out, ldo, tiles_m, tiles_n, none, g)
+    if (out_i_contig) { if (blocked) SFFN_LAUNCH(true, true); else SFFN_LAUNCH(true, false); }
+    else              { if (blocked) SFFN_LAUNCH(false, true); else SFFN_LAUNCH(false, false); }
+#undef SFFN_LAUNCH
     return hipGetLastError();
 }
 
@@ -518,11 +528,11 @@ hipError_t launch_gemm_vnm_epilogue(const uint16_t* a_vals, const uint8_t* a_met
     if (tiles == 0) return hipSuccess;
     dim3 grid(tiles);
     if (ep.mode == 1)
-        hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 1>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
-                           tiles_m, tiles_n, 1, ep, g);
+        hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 1, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
+                           tiles_m, tiles_n, ep, g);
     else
-        hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 2>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
-                           tiles_m, tiles_n, 1, ep, g);
+        hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 2, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
+                           tiles_m, tiles_n, ep, g);
     return hipGetLastError();
 }
 

@@ -41,12 +41,10 @@ struct GemmGroup {
 
 hipError_t launch_prune24(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
                           uint8_t* meta, hipStream_t stream);
-// v24blk / m24blk (both or neither): also write the result as a plain 2:4 matrix over all F columns in the
-// blocked operand layout (common.hpp), ready to be the sparse operand of the GEMMs.
 hipError_t launch_sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, uint16_t* vals, uint8_t* meta,
-                                      uint8_t* colidx, uint16_t* v24blk, uint8_t* m24blk, hipStream_t s);
+                                      uint8_t* colidx, hipStream_t s);
 hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, const uint8_t* colidx,
-                              int64_t T, int64_t F, uint16_t* dvals, uint16_t* v24blk, uint8_t* m24blk, hipStream_t s);
+                              int64_t T, int64_t F, uint16_t* dvals, hipStream_t s);
 // 2:4 prune-and-pack for the fused step: canonical outputs plus the blocked copies the GEMMs read;
 // trans = 1 can also emit a blocked copy of the source matrix itself (rows = its rows, K = its columns).
 // batch > 1 (trans = 1 only): `batch` matrices of the same shape, consecutive in every argument.

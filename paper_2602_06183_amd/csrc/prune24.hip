@@ -93,7 +93,9 @@ __global__ void __launch_bounds__(256) prune24_cols_kernel(const uint16_t* __res
         uint16_t* vb = vblk + blk_off(r, (k0 + 32 * q) / 2, K / 64);
         *reinterpret_cast<uint4*>(vb) = make_uint4(ov[0], ov[1], ov[2], ov[3]);
         *reinterpret_cast<uint4*>(vb + 8) = make_uint4(ov[4], ov[5], ov[6], ov[7]);
-        *reinterpret_cast<uint32_t*>(mblk + mblk_off(r, k0 + 32 * q, K / 64)) = mbytes;
+        // 32 k = one step of the matrix instruction: its two 16-k halves belong to different lanes of the unit
+        *reinterpret_cast<uint16_t*>(mblk + mblk_off(r, k0 + 32 * q, K / 64)) = (uint16_t)mbytes;
+        *reinterpret_cast<uint16_t*>(mblk + mblk_off(r, k0 + 32 * q + 16, K / 64)) = (uint16_t)(mbytes >> 16);
     }
 }
 

@@ -26,8 +26,7 @@ __device__ __forceinline__ uint32_t sqrelu_pair(uint32_t w) {
 // contiguous 1 KB (loads), 256 B (values) or 32 B (metadata) run.
 __global__ void __launch_bounds__(256) sqrelu_vnm_compress_kernel(const uint16_t* __restrict__ y1, int64_t F, int nblk,
                                                                  uint16_t* __restrict__ vals, uint8_t* __restrict__ meta,
-                                                                 uint8_t* __restrict__ colidx, uint16_t* __restrict__ v24blk,
-                                                                 uint8_t* __restrict__ m24blk) {
+                                                                 uint8_t* __restrict__ colidx) {
     __shared__ float s_score[8][64];
     __shared__ uint32_t s_col[64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -94,25 +93,13 @@ __global__ void __launch_bounds__(256) sqrelu_vnm_compress_kernel(const uint16_t
             *reinterpret_cast<uint32_t*>(vals + row * (F / 4) + (int64_t)blk * 2) = v;
             if ((lane & 1) == 0) meta[row * (F / 16) + (blk >> 1)] = (uint8_t)(nib | (other << 4));
         }
-        if (v24blk) {       // the same block as two plain 2:4 groups, in the blocked operand layout of the GEMMs
-            uint32_t a, b, mb;
-            vnm_block_to_24(v, nib, cw, a, b, mb);
-            uint32_t m4 = mb | ((uint32_t)__shfl_down((int)mb, 1, 64) << 8);
-            m4 |= (uint32_t)__shfl_down((int)m4, 2, 64) << 16;
-            if (active) {
-                const int64_t row = row0 + i;
-                *reinterpret_cast<uint2*>(v24blk + blk_off(row, (int64_t)blk * 4, F / 64)) = make_uint2(a, b);
-                if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(m24blk + mblk_off(row, (int64_t)blk * 8, F / 64)) = m4;
-            }
-        }
     }
 }
 
 // eq. (6) evaluated only where y2 was kept.  One thread per (row, column block).
 __global__ void __launch_bounds__(256) dsqrelu_vnm_kernel(const uint16_t* __restrict__ dy2, const uint16_t* __restrict__ y1,
                                                          const uint8_t* __restrict__ meta, const uint8_t* __restrict__ colidx,
-                                                         int64_t F, int nblk, uint16_t* __restrict__ dvals,
-                                                         uint16_t* __restrict__ v24blk, uint8_t* __restrict__ m24blk) {
+                                                         int64_t F, int nblk, uint16_t* __restrict__ dvals) {
     const int blk = blockIdx.x * 256 + threadIdx.x;
     if (blk >= nblk) return;          // nblk is a multiple of 8, so groups of 4 lanes are in or out together
     const int64_t t = blockIdx.y;
@@ -127,14 +114,6 @@ __global__ void __launch_bounds__(256) dsqrelu_vnm_kernel(const uint16_t* __rest
     const float gb = 2.0f * bf2f(pick16(dw, o1)) * (yb > 0.0f ? yb : 0.0f);
     const uint32_t v = f2bf(ga) | (f2bf(gb) << 16);
     *reinterpret_cast<uint32_t*>(dvals + t * (F / 4) + (int64_t)blk * 2) = v;
-    if (v24blk) {
-        uint32_t a, b, mb;
-        vnm_block_to_24(v, nib, cw, a, b, mb);
-        uint32_t m4 = mb | ((uint32_t)__shfl_down((int)mb, 1, 64) << 8);
-        m4 |= (uint32_t)__shfl_down((int)m4, 2, 64) << 16;
-        *reinterpret_cast<uint2*>(v24blk + blk_off(t, (int64_t)blk * 4, F / 64)) = make_uint2(a, b);
-        if ((threadIdx.x & 3) == 0) *reinterpret_cast<uint32_t*>(m24blk + mblk_off(t, (int64_t)blk * 8, F / 64)) = m4;
-    }
 }
 
 // Two survivors per 8 columns leave at most two per aligned group of four, so a V:2:8 matrix is
@@ -235,18 +214,18 @@ __global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* __r
 }
 
 hipError_t launch_sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, uint16_t* vals, uint8_t* meta, uint8_t* colidx,
-                                      uint16_t* v24blk, uint8_t* m24blk, hipStream_t s) {
+                                      hipStream_t s) {
     const int nblk = (int)(F / 8);
     dim3 grid((unsigned)((nblk + 63) / 64), (unsigned)(T / 64));
-    hipLaunchKernelGGL(sqrelu_vnm_compress_kernel, grid, dim3(256), 0, s, y1, F, nblk, vals, meta, colidx, v24blk, m24blk);
+    hipLaunchKernelGGL(sqrelu_vnm_compress_kernel, grid, dim3(256), 0, s, y1, F, nblk, vals, meta, colidx);
     return hipGetLastError();
 }
 
 hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, const uint8_t* colidx, int64_t T,
-                              int64_t F, uint16_t* dvals, uint16_t* v24blk, uint8_t* m24blk, hipStream_t s) {
+                              int64_t F, uint16_t* dvals, hipStream_t s) {
     const int nblk = (int)(F / 8);
     dim3 grid((unsigned)((nblk + 255) / 256), (unsigned)T);
-    hipLaunchKernelGGL(dsqrelu_vnm_kernel, grid, dim3(256), 0, s, dy2, y1, meta, colidx, F, nblk, dvals, v24blk, m24blk);
+    hipLaunchKernelGGL(dsqrelu_vnm_kernel, grid, dim3(256), 0, s, dy2, y1, meta, colidx, F, nblk, dvals);
     return hipGetLastError();
 }
 
