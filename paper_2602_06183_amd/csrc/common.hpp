@@ -7,12 +7,16 @@ namespace sffn {
 
 __device__ __forceinline__ float bf2f(uint32_t h) { return __uint_as_float(h << 16); }
 
-// fp32 -> bf16 bits, round to nearest even; NaN keeps its sign and becomes quiet.
-__device__ __forceinline__ uint32_t f2bf(float f) {
-    uint32_t u = __float_as_uint(f);
-    uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-    return (f != f) ? ((u >> 16) | 0x7FC0u) : r;
+// fp32 -> bf16 bits, round to nearest even, through gfx950's v_cvt_pk_bf16_f32 (checked against integer
+// rounding on every bf16 pattern x tie / near-tie low halves, subnormals included; only NaN payloads differ).
+typedef __attribute__((ext_vector_type(2))) float sffn_f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 sffn_bf16x2;
+__device__ __forceinline__ uint32_t f2bf2(float lo, float hi) {      // -> bf16(lo) | bf16(hi) << 16
+    const sffn_f32x2 v = {lo, hi};
+    const sffn_bf16x2 b = __builtin_convertvector(v, sffn_bf16x2);
+    return __builtin_bit_cast(uint32_t, b);
 }
+__device__ __forceinline__ uint32_t f2bf(float f) { return f2bf2(f, 0.0f) & 0xFFFFu; }
 
 // 2:4 selection on one group of four bf16 (a0..a3 as 16-bit patterns): rank by magnitude
 // descending, index ascending; the two first survive (Section 2.2 of the paper, with the tie rule
@@ -36,8 +40,8 @@ __device__ __forceinline__ uint32_t select24(uint32_t a0, uint32_t a1, uint32_t 
         const uint32_t tm = (r0 == 2) ? m0 : (r1 == 2) ? m1 : (r2 == 2) ? m2 : m3;
         const float t = bf2f(tm);
         const float f0 = bf2f(v0), f1 = bf2f(v1);
-        v0 = f2bf((v0 & 0x8000u) ? f0 + t : f0 - t);
-        v1 = f2bf((v1 & 0x8000u) ? f1 + t : f1 - t);
+        nib = p0 | (p1 << 2);
+        return f2bf2((v0 & 0x8000u) ? f0 + t : f0 - t, (v1 & 0x8000u) ? f1 + t : f1 - t);
     }
     nib = p0 | (p1 << 2);
     return v0 | (v1 << 16);

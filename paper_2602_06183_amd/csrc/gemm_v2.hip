@@ -66,12 +66,11 @@ struct Cfg {
 
 // bf16 bits -> max(y, 0)^2 rounded to bf16 (RNE), returned as the fp32 bit pattern (low half zero).
 // r * r is never NaN here (a NaN input fails the comparison and becomes 0), so no NaN path is needed.
-__device__ __forceinline__ uint32_t sqrelu_hi(uint32_t y) {
+__device__ __forceinline__ uint32_t sqrelu16(uint32_t y) {
     const float f = bf2f(y), r = f > 0.0f ? f : 0.0f;
-    const uint32_t u = __float_as_uint(r * r);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;
+    return f2bf(r * r);
 }
-__device__ __forceinline__ uint32_t sqrelu16(uint32_t y) { return sqrelu_hi(y) >> 16; }
+__device__ __forceinline__ uint32_t sqrelu_hi(uint32_t y) { return sqrelu16(y) << 16; }
 // ordering point between LDS writes and reads of lanes of the same wavefront (its LDS operations execute in
 // issue order; this only stops the compiler from moving them)
 __device__ __forceinline__ void wave_lds_sync() {
@@ -345,7 +344,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             v0 += bb.x; v1 += bb.y; v2 += bb.z; v3 += bb.w;
                         }
                         *reinterpret_cast<uint2*>(scratch + (b * 32 + l32) * EP + il * 2) =
-                            make_uint2(f2bf(v0) | (f2bf(v1) << 16), f2bf(v2) | (f2bf(v3) << 16));
+                            make_uint2(f2bf2(v0, v1), f2bf2(v2, v3));
                     }
             if (EPI != 0) {
 #pragma unroll
@@ -427,7 +426,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             const float d1 = bf2f(*reinterpret_cast<const uint16_t*>(row + q1 * 2));
                             const float ya = bf2f(yk & 0xFFFFu), yb = bf2f(yk >> 16);
                             const float ga = 2.0f * d0 * (ya > 0.0f ? ya : 0.0f), gb = 2.0f * d1 * (yb > 0.0f ? yb : 0.0f);
-                            v = f2bf(ga) | (f2bf(gb) << 16);
+                            v = f2bf2(ga, gb);
                             vals_p[(int64_t)it * 8 * (F / 8)] = v;
                         }
                         // the same block as two plain 2:4 groups (blocked operand of eq. (3) / eq. (7))

@@ -16,7 +16,7 @@ __device__ __forceinline__ uint32_t pick16(const uint32_t (&w)[4], uint32_t c) {
 __device__ __forceinline__ uint32_t sqrelu_pair(uint32_t w) {
     const float a = bf2f(w & 0xFFFFu), b = bf2f(w >> 16);
     const float ra = a > 0.0f ? a : 0.0f, rb = b > 0.0f ? b : 0.0f;
-    return f2bf(ra * ra) | (f2bf(rb * rb) << 16);
+    return f2bf2(ra * ra, rb * rb);
 }
 
 // One workgroup = 64 rows (one V block) x 64 column blocks (512 columns).  Wave w holds rows
@@ -112,7 +112,7 @@ __global__ void __launch_bounds__(256) dsqrelu_vnm_kernel(const uint16_t* __rest
     const float ya = bf2f(pick16(yw, o0)), yb = bf2f(pick16(yw, o1));
     const float ga = 2.0f * bf2f(pick16(dw, o0)) * (ya > 0.0f ? ya : 0.0f);
     const float gb = 2.0f * bf2f(pick16(dw, o1)) * (yb > 0.0f ? yb : 0.0f);
-    const uint32_t v = f2bf(ga) | (f2bf(gb) << 16);
+    const uint32_t v = f2bf2(ga, gb);
     *reinterpret_cast<uint32_t*>(dvals + t * (F / 4) + (int64_t)blk * 2) = v;
 }
 
