@@ -42,7 +42,7 @@ int g_prof_n = 0;
 struct FullLayout {
     sffn_ws_layout pub;
     // internal operands of the GEMMs, all in the blocked layout
-    size_t w1_vblk, w1_mblk, w2t_vblk, w2t_mblk, x_blk, xt_blk, dy_blk, dyt_blk, w2_blk, w1t_blk, a24_vblk, a24_mblk, at_blk, total;
+    size_t w1_vblk, w1_mblk, w2t_vblk, w2t_mblk, x_blk, xt_blk, dy_blk, dyt_blk, w2_blk, w1t_blk, a24_vblk, a24_mblk, at_blk, kmask, total;
 };
 
 // E = number of experts (1 for the plain step): every weight-shaped tensor holds E matrices back to back.
@@ -65,7 +65,8 @@ bool make_layout(const sffn_cfg* c, FullLayout* L, int n_experts = 1) {
     L->dy_blk = take(T * D * 2);           L->dyt_blk = take(D * T * 2);
     L->w2_blk = take(D * F * 2);           L->w1t_blk = take(D * F * 2);
     L->a24_vblk = take(TF);             L->a24_mblk = take(TF / 8);
-    L->at_blk = take(TF * 2);
+    L->at_blk = take(TF);               // transposed activation, compacted to the kept hidden units: [F / 2, T]
+    L->kmask = take(TF / 64 / 8);       // kept-column bit mask per (64-token block, group of 8 hidden units)
     L->total = off;
     L->pub.total = off;
     return true;
@@ -254,6 +255,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     uint16_t* w2b = (uint16_t*)(ws + L.w2_blk);         uint16_t* w1tb = (uint16_t*)(ws + L.w1t_blk);
     uint16_t* a24v = (uint16_t*)(ws + L.a24_vblk);      uint8_t* a24m = ws + L.a24_mblk;
     uint16_t* atb = (uint16_t*)(ws + L.at_blk);
+    uint8_t* kmask = ws + L.kmask;
     uint16_t* ykept = (uint16_t*)(ws + L.pub.y1_kept);
     const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
     // the three ways a token segment meets its expert's weights (see GemmGroup)
@@ -275,7 +277,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, w1v, w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
     {   // eq. (1), then eq. (2) + V:N:M compression on the tile while it is still in LDS
         VnmEpilogue ep;
-        ep.mode = 1; ep.store_dense = keep_dense; ep.vals = y2v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
+        ep.mode = 1; ep.store_dense = keep_dense; ep.vals = y2v; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
         ep.v24 = a24v; ep.m24 = a24m; ep.at = atb;
         STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s, gp), "step/y1+sqrelu_vnm_compress");
     }
@@ -283,7 +285,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     STAGE(launch_gemm_nt_blocked(1, a24v, a24m, w2b, nullptr, T, D, F, 0, Y3, D, s, gd), "step/y3");            // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
     STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
-    STAGE(launch_gemm_nt_blocked(0, atb, nullptr, dytb, nullptr, F, D, T, 1, dW2, F, s, gw), "step/dW2");       // eq. (5)
+    STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");                          // eq. (5)
     {   // eq. (4), then eq. (6) on y2's kept slots; overwrites the 2:4 view and the transposed tile with dy1's
         VnmEpilogue ep;
         ep.mode = 2; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
@@ -292,7 +294,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     }
     STAGE(launch_transpose(W1, F, D, D, w1tb, 1, nullptr, s, (int)E), "step/W1.T");
     STAGE(launch_gemm_nt_blocked(1, a24v, a24m, w1tb, nullptr, T, D, F, 0, dX, D, s, gd), "step/dX");           // eq. (7)
-    STAGE(launch_gemm_nt_blocked(0, atb, nullptr, xtb, nullptr, F, D, T, 0, dW1, D, s, gw), "step/dW1");        // eq. (8)
+    STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                           // eq. (8)
     return SFFN_OK;
 }
 

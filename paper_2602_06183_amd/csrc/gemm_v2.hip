@@ -8,47 +8,11 @@
 // Register layouts of the two instructions are documented in gemm.hip.
 #include "common.hpp"
 #include "kernels.hpp"
+#include "lds_dma.hpp"
 
 namespace sffn {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-
 namespace {
-
-union Frag8 { uint4 u; bf16x8 v; };
-union Frag16 { uint4 u[2]; bf16x16 v; };
-
-typedef __attribute__((address_space(3))) void lds_void;
-typedef const __attribute__((address_space(1))) void glb_void;
-
-// The LDS-DMA loads are issued through inline assembly so that their completion is tracked only by the
-// explicit vmcnt waits of the main loop (the ring keeps the loads of the next tiles in flight across
-// the fragment reads of the current one).  m0 carries the wave-uniform LDS destination.  The source is
-// a wave-uniform 64-bit base in SGPRs plus a 32-bit per-lane byte offset: with per-lane 64-bit VGPR
-// addresses the loads crawl while the matrix cores are busy (measured: smfmac + DMA 1.22 us per step
-// against 0.76 us in this form, 0.67 us for the smfmacs alone).
-__device__ __forceinline__ uint64_t uniform64(const void* p) {
-    const uint64_t v = (uint64_t)(uintptr_t)p;
-    return ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(v >> 32)) << 32) |
-           (uint32_t)__builtin_amdgcn_readfirstlane((int)(v & 0xFFFFFFFFu));
-}
-__device__ __forceinline__ void dma16(uint64_t base, uint32_t lane_off, unsigned char* lds_wave_base) {
-    // every lane fetches 16 bytes at base + lane_off; the wave's 64 chunks land at lds_wave_base + 16 * lane
-    const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void*)lds_wave_base);
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(dst) : "m0", "memory");
-}
-__device__ __forceinline__ void dma4(uint64_t base, uint32_t lane_off, unsigned char* lds_wave_base) {
-    const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void*)lds_wave_base);
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(lane_off), "s"(base), "s"(dst) : "m0", "memory");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    // gfx9 s_waitcnt immediate: vmcnt = bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8 (left at "no wait")
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
-}
 
 template <bool SPARSE>
 struct Cfg {
@@ -71,14 +35,6 @@ __device__ __forceinline__ uint32_t sqrelu16(uint32_t y) {
     return f2bf(r * r);
 }
 __device__ __forceinline__ uint32_t sqrelu_hi(uint32_t y) { return sqrelu16(y) << 16; }
-// ordering point between LDS writes and reads of lanes of the same wavefront (its LDS operations execute in
-// issue order; this only stops the compiler from moving them)
-__device__ __forceinline__ void wave_lds_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 template <bool SPARSE, bool OUT_I_CONTIG, int EPI, bool BLOCKED>
 __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restrict__ a_vals, const uint8_t* __restrict__ a_meta,
                                                         const uint16_t* __restrict__ B, const float* __restrict__ bias,
@@ -293,7 +249,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         mma_row(P, 3, false); SB();
         // Q has arrived and tile kt+1 has landed (this wave's part); after the barrier every wave is done
         // reading this stage, which is refilled at once, and every wave's part of tile kt+1 is in LDS
-        __builtin_amdgcn_s_waitcnt(((C::NSTAGE - 2) * C::LOADS & 0xF) | ((((C::NSTAGE - 2) * C::LOADS) >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
+        wait_vmcnt_lgkm0<(C::NSTAGE - 2) * C::LOADS>();
         __builtin_amdgcn_s_barrier();
         SB();
         mma_row(Q, 0, true); SB();
@@ -316,7 +272,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         // through LDS as [j][i] (two halves of 64 i) so that HBM sees 128-byte row segments instead of
         // 16-byte ones; the bias (indexed by i) is added before the single rounding to bf16.
         constexpr int EP = 64 * 2 + 16;
-        constexpr int WAVE_LDS = (EPI != 0) ? 2 * WN * EP : WN * EP;     // EPI: second tile for the transposed output
+        constexpr int WAVE_LDS = (EPI != 0) ? (WN + 32) * EP : WN * EP;  // EPI: second tile (32 compact rows) for the transposed output
         unsigned char* scratch = smem + wave * WAVE_LDS;
         static_assert(8 * WAVE_LDS <= C::NSTAGE * C::STAGE, "epilogue scratch must fit in the main-loop LDS");
         unsigned char* ttile = scratch + WN * EP;
@@ -348,7 +304,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                     }
             if (EPI != 0) {
 #pragma unroll
-                for (int q = 0; q < WN * EP / 1024; ++q) *reinterpret_cast<uint4*>(ttile + (q * 64 + lane) * 16) = make_uint4(0, 0, 0, 0);
+                for (int q = 0; q < (32 * EP + 1023) / 1024; ++q)
+                    if ((q * 64 + lane) * 16 < 32 * EP) *reinterpret_cast<uint4*>(ttile + (q * 64 + lane) * 16) = make_uint4(0, 0, 0, 0);
             }
             wave_lds_sync();
             if (EPI == 0 || ep.store_dense) {
@@ -383,7 +340,10 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                     for (int c = 0; c < 8; ++c)
                         if ((bits >> c) & 1u) { mine |= (uint32_t)c << (8 * n); ++n; }
                     if (valid && bl == 0)
+                    {
                         *reinterpret_cast<uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblk + (f0 >> 3) + (lane >> 3)) * 4) = mine;
+                        ep.kmask[(int64_t)(t0 >> 6) * nblk + (f0 >> 3) + (lane >> 3)] = (uint8_t)bits;
+                    }
                     cw = (uint32_t)__shfl((int)mine, bl * 8, 64);
                 } else {
                     cw = valid ? *reinterpret_cast<const uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblk + blk_g) * 4) : 0x03020100u;
@@ -435,18 +395,18 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         const uint32_t m2 = mb8 | (row_shl<1>(mb8) << 8);     // two column blocks = 16 k = one lane's half-word of a unit
                         *reinterpret_cast<uint2*>(v24_p + (int64_t)(it >> 1) * (F / 64) * 512 + (it & 1) * 256) = make_uint2(a24, b24);
                         if ((lane & 1) == 0) *reinterpret_cast<uint16_t*>(m24_p + (int64_t)(it >> 2) * (F / 64) * 256 + (it & 3) * 32) = (uint16_t)m2;
-                        // dense transposed tile for the weight-gradient GEMM: row = hidden unit, column = token
-                        const uint32_t o0 = (cw >> (8 * (nib & 3u))) & 0xFFu, o1 = (cw >> (8 * (nib >> 2))) & 0xFFu;
-                        *reinterpret_cast<uint16_t*>(ttile + (bl * 8 + o0) * EP + t * 2) = (uint16_t)(v & 0xFFFFu);
-                        *reinterpret_cast<uint16_t*>(ttile + (bl * 8 + o1) * EP + t * 2) = (uint16_t)(v >> 16);
+                        // transposed tile for the weight-gradient GEMM, compacted to the block's four kept hidden units:
+                        // row = 4 * block + position among the kept units, column = token
+                        *reinterpret_cast<uint16_t*>(ttile + (bl * 4 + (nib & 3u)) * EP + t * 2) = (uint16_t)(v & 0xFFFFu);
+                        *reinterpret_cast<uint16_t*>(ttile + (bl * 4 + (nib >> 2)) * EP + t * 2) = (uint16_t)(v >> 16);
                     }
                 }
                 wave_lds_sync();
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {          // 4 groups of 16 hidden units x 2 chunks of 32 tokens, 1 KB each
+                for (int q = 0; q < 4; ++q) {          // 2 groups of 16 compact rows x 2 chunks of 32 tokens, 1 KB each
                     const int fr = (q >> 1) * 16 + (lane >> 2), tc = (q & 1) * 32 + (lane & 3) * 8;
                     if (valid)
-                        *reinterpret_cast<uint4*>(ep.at + blk_off(f0 + fr, t0 + tc, tok_ld / 32)) = *reinterpret_cast<const uint4*>(ttile + fr * EP + tc * 2);
+                        *reinterpret_cast<uint4*>(ep.at + blk_off(f0 / 2 + fr, t0 + tc, tok_ld / 32)) = *reinterpret_cast<const uint4*>(ttile + fr * EP + tc * 2);
                 }
             }
             wave_lds_sync();

@@ -8,7 +8,8 @@ namespace sffn {
 // Fused V:N:M epilogue of the two GEMMs whose output feeds the activation sparsifier (ffn_sparse_step only).
 //   mode 1 (eq. (1) -> eq. (2) + Section 2.3): the tile of y1 is squared-ReLU'd and compressed in place: outputs the
 //          canonical V:N:M y2 (vals, meta, colidx), y1 at the kept slots (ykept, same indexing as vals), the plain
-//          2:4 view (v24, m24; blocked layout) and the dense transposed y2v (at; blocked layout, rows = F).
+//          2:4 view (v24, m24; blocked layout) and the transposed y2v compacted to the four kept hidden units of every
+//          (64-token block, group of 8) (at; [F / 2, T], blocked layout; see gemm_wgrad.hip).
 //   mode 2 (eq. (4) -> eq. (6)): the tile of dy2 meets (meta, colidx, ykept) and becomes dy1 in y2's slots: outputs
 //          vals (= dy1 values), v24 / m24 and at as above.
 //   store_dense: also write the dense GEMM output (y1 / dy2) to `out`.
@@ -18,6 +19,7 @@ struct VnmEpilogue {
     uint16_t* vals = nullptr;
     uint8_t* meta = nullptr;
     uint8_t* colidx = nullptr;
+    uint8_t* kmask = nullptr;       // mode 1: one byte per (64-token block, group of 8): bit c = column c of the group is kept
     uint16_t* ykept = nullptr;
     uint16_t* v24 = nullptr;
     uint8_t* m24 = nullptr;
@@ -73,6 +75,12 @@ hipError_t launch_gemm_nt_blocked(int sparse_a, const uint16_t* a_vals, const ui
                                   const GemmGroup* grp = nullptr);
 hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
                           int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
+
+// eqs. (5), (8): C[f, n] = sum_t A[t, f] * G[t, n] with A given as `atc` (compacted transposed activation written by the
+// V:N:M epilogue) + kmask (kept-column bit masks, [T / 64, F / 8]), G = [N rows, T] in the blocked layout; out_i_contig: out[n * ldo + f], else out[f * ldo + n].
+// grp (role 2): every expert contracts over its own token segment into its own output (out_stride).
+hipError_t launch_wgrad_vnm(const uint16_t* atc, const uint8_t* kmask, const uint16_t* G, int64_t F, int64_t N, int64_t T,
+                            int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 
 extern int g_tile_sparse, g_tile_dense;
 
