@@ -46,7 +46,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     constexpr int BM = C::BM, BN = C::BN, WM = 128, WN = 64, FM = 4, FN = 2;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[C::NSTAGE * C::STAGE];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: everything derived from it stays in SGPRs
     const int wm = wave >> 2, wn = wave & 3;
     const int l32 = lane & 31, lh = lane >> 5;
 
@@ -142,15 +143,18 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         unsigned char* sa = smem + stage * C::STAGE;
         unsigned char* sb = sa + C::A_BYTES;
         unsigned char* sm = sb + C::B_BYTES;
+        // the k position goes into the 32-bit per-lane offset (one vector add per operand); the bases stay put in SGPRs
         if (h == 0) {
+            const uint32_t ao = a_lane + (uint32_t)kt * a_kstep, bo = b_lane + (uint32_t)kt * b_kstep;
 #pragma unroll
-            for (int n = 0; n < A_LD; ++n) dma16(a_base[n] + (uint64_t)kt * a_kstep, a_lane, sa + (wave * A_LD + n) * 1024);
+            for (int n = 0; n < A_LD; ++n) dma16(a_base[n], ao, sa + (wave * A_LD + n) * 1024);
 #pragma unroll
-            for (int n = 0; n < B_LD / 2; ++n) dma16(b_base[n] + (uint64_t)kt * b_kstep, b_lane, sb + (wave * B_LD + n) * 1024);
+            for (int n = 0; n < B_LD / 2; ++n) dma16(b_base[n], bo, sb + (wave * B_LD + n) * 1024);
         } else {
+            const uint32_t bo = b_lane + (uint32_t)kt * b_kstep;
 #pragma unroll
-            for (int n = B_LD / 2; n < B_LD; ++n) dma16(b_base[n] + (uint64_t)kt * b_kstep, b_lane, sb + (wave * B_LD + n) * 1024);
-            if (SPARSE) dma4(m_base + (uint64_t)kt * m_kstep, m_lane, sm + wave * 256);
+            for (int n = B_LD / 2; n < B_LD; ++n) dma16(b_base[n], bo, sb + (wave * B_LD + n) * 1024);
+            if (SPARSE) dma4(m_base, m_lane + (uint32_t)kt * m_kstep, sm + wave * 256);
         }
     };
     auto issue = [&](int kt, int stage) { issue_half(kt, stage, 0); issue_half(kt, stage, 1); };

@@ -36,7 +36,8 @@ __global__ void __launch_bounds__(512) wgrad_vnm_kernel(const uint16_t* __restri
     constexpr int BM = 256, BN = 256, WM = 128, WN = 64, FM = 4, FN = 2;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kStages * kStage];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 2, wn = wave & 3;
     const int l32 = lane & 31, lh = lane >> 5;
 
@@ -95,15 +96,16 @@ __global__ void __launch_bounds__(512) wgrad_vnm_kernel(const uint16_t* __restri
         unsigned char* sa = smem + stage * kStage;
         unsigned char* sb = sa + kABytes;
         unsigned char* sc = sb + kBBytes;
+        const uint32_t o = blk_lane + (uint32_t)kt * 2048;      // k position in the per-lane offset; bases stay in SGPRs
         if (h == 0) {
-            dma4(c_base + (uint64_t)kt * c_kstep, c_lane, sc + wave * 256);     // first: the look-up wants it earliest
-            dma16(a_base[0] + (uint64_t)kt * 2048, blk_lane, sa + wave * 1024);
-            dma16(a_base[1] + (uint64_t)kt * 2048, blk_lane, sa + kAHalf + wave * 1024);
-            dma16(b_base[0] + (uint64_t)kt * 2048, blk_lane, sb + (wave * 4 + 0) * 1024);
-            dma16(b_base[1] + (uint64_t)kt * 2048, blk_lane, sb + (wave * 4 + 1) * 1024);
+            dma4(c_base, c_lane + (uint32_t)kt * c_kstep, sc + wave * 256);     // first: the look-up wants it earliest
+            dma16(a_base[0], o, sa + wave * 1024);
+            dma16(a_base[1], o, sa + kAHalf + wave * 1024);
+            dma16(b_base[0], o, sb + (wave * 4 + 0) * 1024);
+            dma16(b_base[1], o, sb + (wave * 4 + 1) * 1024);
         } else {
-            dma16(b_base[2] + (uint64_t)kt * 2048, blk_lane, sb + (wave * 4 + 2) * 1024);
-            dma16(b_base[3] + (uint64_t)kt * 2048, blk_lane, sb + (wave * 4 + 3) * 1024);
+            dma16(b_base[2], o, sb + (wave * 4 + 2) * 1024);
+            dma16(b_base[3], o, sb + (wave * 4 + 3) * 1024);
         }
     };
 
