@@ -36,7 +36,7 @@ def executed_flops(stage, T, D, F):
 
 KERNEL_OF_STAGE = {"step/y1+sqrelu_vnm_compress": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dy2+dsqrelu_vnm": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
                    "step/y3": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dX": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
-                   "step/dW2": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>", "step/dW1": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>"}
+                   "step/dW2": "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>", "step/dW1": "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>"}
 
 
 def main():
