@@ -289,6 +289,18 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         for (int h = 0; h < 2; ++h) {
             const int f0 = i0 + wm * WM + h * 64;
             const bool valid = t0 < Rb && f0 < Ra;
+            // the lane's 32 bias values of this half, fetched together (one wait instead of one per store)
+            float4 bb[2][4];
+#pragma unroll
+            for (int a2 = 0; a2 < 2; ++a2)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bb[a2][g] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (bias) {
+                        int i = f0 + a2 * 32 + 8 * g + 4 * lh; i = i < Ra ? i : Ra - 4;
+                        bb[a2][g] = *reinterpret_cast<const float4*>(bias + i);
+                    }
+                }
 #pragma unroll
             for (int a2 = 0; a2 < 2; ++a2)
 #pragma unroll
@@ -297,12 +309,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                     for (int g = 0; g < 4; ++g) {
                         const int a = 2 * h + a2;
                         const int il = a2 * 32 + 8 * g + 4 * lh;              // i inside the 64-wide half
-                        float v0 = acc[a][b][4 * g], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2], v3 = acc[a][b][4 * g + 3];
-                        if (bias) {
-                            int i = f0 + il; i = i < Ra ? i : Ra - 4;
-                            const float4 bb = *reinterpret_cast<const float4*>(bias + i);
-                            v0 += bb.x; v1 += bb.y; v2 += bb.z; v3 += bb.w;
-                        }
+                        const float v0 = acc[a][b][4 * g] + bb[a2][g].x, v1 = acc[a][b][4 * g + 1] + bb[a2][g].y;
+                        const float v2 = acc[a][b][4 * g + 2] + bb[a2][g].z, v3 = acc[a][b][4 * g + 3] + bb[a2][g].w;
                         *reinterpret_cast<uint2*>(scratch + (b * 32 + l32) * EP + il * 2) =
                             make_uint2(f2bf2(v0, v1), f2bf2(v2, v3));
                     }
@@ -359,6 +367,14 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                 uint16_t* v24_p = ep.v24 + blk_off(t0 + (lane >> 3), blk_g * 4, F / 64);
                 uint8_t* m24_p = ep.m24 + mblk_off(t0 + (lane >> 3), blk_g * 8, F / 64);
                 const uint32_t c0 = (cw & 0xFFu) * 2, c1 = ((cw >> 8) & 0xFFu) * 2, c2 = ((cw >> 16) & 0xFFu) * 2, c3 = (cw >> 24) * 2;
+                uint32_t pre_m[8], pre_y[8];                                // EPI 2: saved metadata and y1 of the 8 sweeps, fetched together
+                if (EPI == 2 && valid) {
+#pragma unroll
+                    for (int it = 0; it < 8; ++it) {
+                        pre_m[it] = meta_p[(int64_t)it * 8 * (F / 16)];
+                        pre_y[it] = kept_p[it * 64];
+                    }
+                }
                 if (valid) {
 #pragma unroll
                     for (int it = 0; it < 8; ++it) {
@@ -382,8 +398,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             mw |= row_shl<4>(mw) << 16;
                             if (bl == 0) *reinterpret_cast<uint32_t*>(meta_p + (int64_t)it * 8 * (F / 16)) = mw;
                         } else {
-                            const uint32_t mb = meta_p[(int64_t)it * 8 * (F / 16)];
-                            const uint32_t yk = kept_p[it * 64];
+                            const uint32_t mb = pre_m[it];
+                            const uint32_t yk = pre_y[it];
                             nib = (mb >> (4 * (bl & 1))) & 0xFu;
                             const uint32_t q0 = (cw >> (8 * (nib & 3u))) & 0xFFu, q1 = (cw >> (8 * (nib >> 2))) & 0xFFu;
                             const float d0 = bf2f(*reinterpret_cast<const uint16_t*>(row + q0 * 2));
