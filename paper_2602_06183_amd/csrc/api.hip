@@ -282,7 +282,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
         STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s, gp), "step/y1+sqrelu_vnm_compress");
     }
     STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, w2v, w2m, w2vb, w2mb, w2b, s, (int)E), "step/prune24(W2.T)");
-    STAGE(launch_gemm_nt_blocked(1, a24v, a24m, w2b, nullptr, T, D, F, 0, Y3, D, s, gd), "step/y3");            // eq. (3)
+    STAGE(launch_spmm_blocked(a24v, a24m, w2b, nullptr, T, D, F, 0, Y3, D, s, gd), "step/y3");            // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
     STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
     STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");                          // eq. (5)
@@ -293,7 +293,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
         STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, ep, s, gp), "step/dy2+dsqrelu_vnm");
     }
     STAGE(launch_transpose(W1, F, D, D, w1tb, 1, nullptr, s, (int)E), "step/W1.T");
-    STAGE(launch_gemm_nt_blocked(1, a24v, a24m, w1tb, nullptr, T, D, F, 0, dX, D, s, gd), "step/dX");           // eq. (7)
+    STAGE(launch_spmm_blocked(a24v, a24m, w1tb, nullptr, T, D, F, 0, dX, D, s, gd), "step/dX");           // eq. (7)
     STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                           // eq. (8)
     return SFFN_OK;
 }

@@ -1,10 +1,11 @@
-// Pipelined tile kernel for the six contractions: C[i, j] = sum_k A[i, k] * B[j, k] with a 256 x 256
-// workgroup tile, 8 wavefronts (2 along i x 4 along j, 128 x 64 each, two wavefronts per SIMD so one
-// hides the other's LDS latency), operand tiles streamed HBM -> LDS with global_load_lds_dwordx4 into
-// a ring of LDS stages (no register staging), XOR-swizzled 16-byte chunks so that the b128 fragment
-// reads are bank-conflict free without padding.
-//   SPARSE: A packed 2:4 -> v_smfmac_f32_32x32x32_bf16; ring of 3 stages of 64 k (50 KB each).
-//   dense : v_mfma_f32_32x32x16_bf16; ring of 4 stages of 32 k (32 KB each).
+// Pipelined tile kernel: C[i, j] = sum_k A[i, k] * B[j, k] with a 256 x 256 workgroup tile, 8 wavefronts
+// (2 along i x 4 along j, 128 x 64 each, two wavefronts per SIMD so one hides the other's LDS latency), operand
+// tiles streamed HBM -> LDS with global_load_lds_dwordx4 into a ring of LDS stages (no register staging),
+// XOR-swizzled 16-byte chunks so that the b128 fragment reads are bank-conflict free without padding.
+//   SPARSE: A packed 2:4 -> v_smfmac_f32_32x32x32_bf16; ring of 3 stages of 64 k (50 KB each).  Eqs. (1), (3), (4), (7):
+//           in the fused step on blocked operands (eqs. (1), (4) with the V:N:M epilogue), stand-alone on row-major ones.
+//   dense : v_mfma_f32_32x32x16_bf16; ring of 4 stages of 32 k (32 KB each); row-major operands only (stand-alone
+//           vnm_wgrad; the fused step's weight gradients have their own kernel, gemm_wgrad.hip).
 // Register layouts of the two instructions are documented in gemm.hip.
 #include "common.hpp"
 #include "kernels.hpp"
@@ -59,18 +60,12 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         L = (pid < per * 8) ? (pid & 7) * per + (pid >> 3) : pid;
     }
     // Grouped form: find the expert of this tile and narrow the problem to its token segment.
-    const int Kld = K;                   // K extent of the stored operands (block-row stride); K becomes the loop length
+    const int Kld = K;                   // K extent of the stored operands (block-row stride)
     const int tok_ld = grp.n ? grp.seg[grp.n] : Rb;       // tokens in the token-indexed outputs of the V:N:M epilogue
-    int i_base = 0, j_base = 0, k_base = 0;
+    int i_base = 0, j_base = 0;
     if (grp.n) {
         int e = 0;
-        if (grp.role == 2) {
-            const int per = tiles_m * tiles_n;
-            e = L / per;
-            L -= e * per;
-            k_base = grp.seg[e];
-            K = grp.seg[e + 1] - k_base;
-        } else {
+        {
             const int other = grp.role == 0 ? tiles_n : tiles_m;
             int cnt = 0;
             for (; e < grp.n; ++e) {
@@ -112,18 +107,17 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         const int rb = lane >> 2;                                        // row inside the 16-row group
         const int c = (lane & 3) ^ ((rb >> 2) & 3);                      // source chunk for this lane's LDS slot
         const int KCa = SPARSE ? Kld / 64 : Kld / 32, KCb = Kld / 32;    // 32-element chunks per row
-        const int64_t ka = (int64_t)(SPARSE ? k_base / 64 : k_base / 32) << 9, kb = (int64_t)(k_base / 32) << 9;   // blocked only (grouped)
 #pragma unroll
         for (int n = 0; n < A_LD; ++n) {
             int gr = i0 + (wave * A_LD + n) * 16; gr = gr < Ra ? gr : Ra - 16;
-            a_base[n] = uniform64(blocked ? a_vals + ((int64_t)(gr >> 4) * KCa << 9) + ka : a_vals + (int64_t)gr * lda);
+            a_base[n] = uniform64(blocked ? a_vals + ((int64_t)(gr >> 4) * KCa << 9) : a_vals + (int64_t)gr * lda);
         }
 #pragma unroll
         for (int n = 0; n < B_LD; ++n) {
             // SPARSE: a stage holds 64 k of B as two half-tiles (k 0-31, k 32-63), each laid out like the A tile
             const int bk = wave * B_LD + n, h = SPARSE ? (bk >> 4) : 0;
             int gr = j0 + (bk & 15) * 16; gr = gr < Rb ? gr : Rb - 16;
-            b_base[n] = uniform64(blocked ? B + (((int64_t)(gr >> 4) * KCb + h) << 9) + kb : B + (int64_t)gr * Kld + h * 32);
+            b_base[n] = uniform64(blocked ? B + (((int64_t)(gr >> 4) * KCb + h) << 9) : B + (int64_t)gr * Kld + h * 32);
         }
         a_lane = blocked ? (rb * 32 + c * 8) * 2 : (uint32_t)(rb * lda + c * 8) * 2;
         b_lane = blocked ? (rb * 32 + c * 8) * 2 : (uint32_t)(rb * Kld + c * 8) * 2;
@@ -132,7 +126,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         m_lane = blocked ? lane * 4 : (uint32_t)((lane >> 1) * (Kld / 8) + (lane & 1) * 4);
         if (SPARSE) {
             int gr = i0 + wave * 32; gr = gr < Ra ? gr : Ra - 32;
-            m_base = uniform64(blocked ? a_meta + (((int64_t)(gr >> 5) * (Kld / 64) + k_base / 64) << 8) : a_meta + (int64_t)gr * (Kld / 8));
+            m_base = uniform64(blocked ? a_meta + ((int64_t)(gr >> 5) * (Kld / 64) << 8) : a_meta + (int64_t)gr * (Kld / 8));
         }
         a_kstep = blocked ? 1024 : 64;
         b_kstep = blocked ? 1024 * (C::BK / 32) : C::BK * 2;
@@ -460,7 +454,6 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
 // Grid of a launch: one workgroup per 256 x 256 output tile; grouped: per expert, over its token segment.
 static unsigned grid_tiles(int tiles_m, int tiles_n, const GemmGroup& g) {
     if (g.n == 0) return (unsigned)(tiles_m * tiles_n);
-    if (g.role == 2) return (unsigned)(g.n * tiles_m * tiles_n);
     int tok_tiles = 0;
     for (int e = 0; e < g.n; ++e) tok_tiles += (g.seg[e + 1] - g.seg[e] + 255) / 256;
     return (unsigned)(tok_tiles * (g.role == 0 ? tiles_n : tiles_m));
@@ -472,15 +465,18 @@ static hipError_t launch_v2(const uint16_t* a_vals, const uint8_t* a_meta, const
                             const GemmGroup* grp) {
     const int tiles_m = (int)((Ra + 255) / 256), tiles_n = (int)((Rb + 255) / 256);
     const GemmGroup g = grp ? *grp : GemmGroup();
-    if (g.n && (!blocked || g.n > GemmGroup::kMaxExperts || (SPARSE && g.role == 2))) return hipErrorInvalidValue;
+    if (g.n && (!blocked || g.n > GemmGroup::kMaxExperts || g.role == 2)) return hipErrorInvalidValue;
     const unsigned tiles = grid_tiles(tiles_m, tiles_n, g);
     if (tiles == 0) return hipSuccess;
     dim3 grid(tiles);
     const VnmEpilogue none;
 #define SFFN_LAUNCH(ICONTIG, BLK) hipLaunchKernelGGL((gemm_nt_v2_kernel<SPARSE, ICONTIG, 0, BLK>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, \
                                                    (int)Ra, (int)Rb, (int)K, out, ldo, tiles_m, tiles_n, none, g)
-    if (out_i_contig) { if (blocked) SFFN_LAUNCH(true, true); else SFFN_LAUNCH(true, false); }
-    else              { if (blocked) SFFN_LAUNCH(false, true); else SFFN_LAUNCH(false, false); }
+    if (blocked) {      // fused step: only eqs. (3), (7) come here (structured-sparse A, tokens along i, j-contiguous output)
+        if constexpr (SPARSE) { if (out_i_contig) return hipErrorInvalidValue; SFFN_LAUNCH(false, true); }
+        else return hipErrorInvalidValue;
+    } else if (out_i_contig) SFFN_LAUNCH(true, false);
+    else SFFN_LAUNCH(false, false);
 #undef SFFN_LAUNCH
     return hipGetLastError();
 }
@@ -491,11 +487,9 @@ hipError_t launch_gemm_nt_v2(int sparse_a, const uint16_t* a_vals, const uint8_t
     return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s, nullptr);
 }
 
-hipError_t launch_gemm_nt_blocked(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
-                                  int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s,
-                                  const GemmGroup* grp) {
-    if (sparse_a) return launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 1, s, grp);
-    return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 1, s, grp);
+hipError_t launch_spmm_blocked(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t Ra, int64_t Rb,
+                               int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp) {
+    return launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 1, s, grp);
 }
 
 hipError_t launch_gemm_vnm_epilogue(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t F,

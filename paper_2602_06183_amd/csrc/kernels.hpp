@@ -64,15 +64,15 @@ hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld
 //   sparse_a: A given as 2:4 packed (a_vals [Ra, K/2], a_meta [Ra, K/8]) and multiplied on the
 //             structured-sparse matrix cores; else a_vals is a dense [Ra, K] matrix.
 //   out_i_contig: 1 -> out[j * ldo + i] (+ bias[i]);  0 -> out[i * ldo + j].
-//   blocked (launch_gemm_nt_blocked): both operands (and the metadata) are in the blocked layout of common.hpp.
+//   launch_spmm_blocked: A packed 2:4; both operands (and the metadata) are in the blocked layout of common.hpp;
+//   out_i_contig must be 0 (eqs. (3), (7) of the fused step).
 // eq. (1) / eq. (4) with the fused epilogue above: A packed 2:4 [Ra = F rows], B = [Rb = T rows], all blocked; out [T, F].
 // grp (optional, blocked launchers only): grouped form, see GemmGroup; Ra / Rb / K then count all tokens on the token axis.
 hipError_t launch_gemm_vnm_epilogue(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t F,
                                     int64_t T, int64_t K, uint16_t* out, const VnmEpilogue& ep, hipStream_t s,
                                     const GemmGroup* grp = nullptr);
-hipError_t launch_gemm_nt_blocked(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
-                                  int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s,
-                                  const GemmGroup* grp = nullptr);
+hipError_t launch_spmm_blocked(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t Ra, int64_t Rb,
+                               int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
                           int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
 
