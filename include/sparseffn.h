@@ -156,9 +156,6 @@ int ffn_sparse_step_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* s
  * most recent step and returns the number of launches, filling ms[i] (duration of launch i) and
  * names[i] (static strings naming the stage).  Not thread-safe; enable/disable create/destroy events. */
 int sffn_profile_enable(int on);
-/* Tuning knob for benchmarking: key 0 = workgroup tile of the structured-sparse GEMMs, key 1 = of the
- * dense GEMMs; value 0: 128x128, 1: 256x128, 2: 128x256, 3: 256x256.  Results do not depend on it. */
-int sffn_tune(int key, int value);
 int sffn_profile_read(float* ms, const char** names, int max_n);
 
 #ifdef __cplusplus

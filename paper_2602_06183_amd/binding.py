@@ -65,10 +65,6 @@ def load():
     lib.ffn_sparse_step_grouped.argtypes = [ctypes.POINTER(_Cfg), i32, ctypes.POINTER(ctypes.c_int64)] + [p] * 9 + [p, sz, p]
     lib.sffn_profile_enable.argtypes = [i32]
     lib.sffn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_char_p), i32]
-    lib.sffn_tune.argtypes = [i32, i32]
-    for key, env in ((0, "SFFN_TILE_SPARSE"), (1, "SFFN_TILE_DENSE")):      # benchmarking knobs
-        if os.environ.get(env):
-            lib.sffn_tune(key, int(os.environ[env]))
     _LIB = lib
     return lib
 

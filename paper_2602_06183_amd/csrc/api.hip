@@ -324,13 +324,6 @@ int ffn_sparse_step_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* s
     return run_step(cfg, n_experts, seg_offsets, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, ws_bytes, stream);
 }
 
-int sffn_tune(int key, int value) {
-    if (key == 0) g_tile_sparse = value;
-    else if (key == 1) g_tile_dense = value;
-    else return fail(SFFN_EINVAL, "%s", "sffn_tune: unknown key");
-    return SFFN_OK;
-}
-
 int sffn_profile_enable(int on) {
     if (on && !g_prof_on) {
         for (int i = 0; i <= kMaxStages; ++i)

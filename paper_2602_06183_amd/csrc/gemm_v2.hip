@@ -6,7 +6,7 @@
 //           in the fused step on blocked operands (eqs. (1), (4) with the V:N:M epilogue), stand-alone on row-major ones.
 //   dense : v_mfma_f32_32x32x16_bf16; ring of 4 stages of 32 k (32 KB each); row-major operands only (stand-alone
 //           vnm_wgrad; the fused step's weight gradients have their own kernel, gemm_wgrad.hip).
-// Register layouts of the two instructions are documented in gemm.hip.
+// Register layouts of the two instructions are documented in lds_dma.hpp.
 #include "common.hpp"
 #include "kernels.hpp"
 #include "lds_dma.hpp"
@@ -481,7 +481,7 @@ static hipError_t launch_v2(const uint16_t* a_vals, const uint8_t* a_meta, const
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_nt_v2(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
+hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
                              int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
     if (sparse_a) return launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s, nullptr);
     return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s, nullptr);

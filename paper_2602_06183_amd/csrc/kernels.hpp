@@ -82,6 +82,5 @@ hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a
 hipError_t launch_wgrad_vnm(const uint16_t* atc, const uint8_t* kmask, const uint16_t* G, int64_t F, int64_t N, int64_t T,
                             int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 
-extern int g_tile_sparse, g_tile_dense;
 
 }  // namespace sffn

@@ -1,4 +1,14 @@
 // LDS-DMA primitives and fragment types shared by the pipelined tile kernels (gemm_v2.hip, gemm_wgrad.hip).
+//
+// Register layouts of the two matrix instructions used there (measured on gfx950 with one-hot operands):
+//   v_smfmac_f32_32x32x32_bf16  A: lane l -> row l%32, survivors 8*(l/32)..+7 of the 16 (k in 16*(l/32)..+15),
+//                                  index VGPR bits [2e+1:2e] = position of survivor e inside its group of 4
+//                                  (ABID 0: bits 15:0 of the VGPR, ABID 1: bits 31:16);
+//                               B: lane l -> column l%32; elements 0-7 = k 8*(l/32)..+7, elements 8-15 = k 16+8*(l/32)..+7;
+//                               D: lane l, register r -> row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+//   v_mfma_f32_32x32x16_bf16    A, B: lane l -> row / column l%32, k 8*(l/32)..+7;  D as above.
+// The 2-bit positions are exactly the packed format's metadata nibbles, so metadata goes from HBM to the index
+// VGPR without re-encoding.
 #pragma once
 #include "common.hpp"
 
