@@ -188,6 +188,21 @@ def main():
         "hbm_peak GB/s": HBM_PEAK_GBS,
     }
 
+    # ---- how much of the activation's L1 mass the V:N:M format keeps (sum of kept y2 / sum of all y2): one extra,
+    #      untimed step that also stores the dense y1; plain torch reductions, measurement only ------------------
+    retained = None
+    if not moe:
+        del y2, dy2, dy1                                   # the dense baseline's buffers are no longer needed
+        chk = sffn.FfnStep(T, D, F, mode, keep_dense=True)
+        chk(X, W1, W2, b1, dY)
+        sv = chk.saved()
+        y2_all = torch.clamp_min(sv["y1"].float(), 0.0).square_().to(torch.bfloat16)        # eq. (2), rounded as the kernel does
+        retained = round(float(sv["y2_vals"].float().sum() / y2_all.float().sum()), 4)
+        zero_frac = round(float((y2_all == 0).float().mean()), 4)
+        del chk, sv, y2_all
+    else:
+        zero_frac = None
+
     # ---- CPU oracle on the host cores: a bounded token sample of the same workload ---------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -224,6 +239,7 @@ def main():
         "second_pass": {"ms_per_step": round(ms_sparse2, 4), "dense_ms_per_step": round(ms_dense2, 4)},
         "stage_ms": {k: round(v, 4) for k, v in acc.items()},
         "standalone_kernels": kernels,
+        "retained_l1_fraction": retained, "relu_zero_fraction": zero_frac,
         "roofline": roofline, "cpu_baseline": cpu,
         "paper_context": "paper reports 1.4-1.5x for 2:4 GEMMs and 1.4-1.7x end-to-end on NVIDIA sparse tensor cores (Sections 1, 5.2.3); context, not a target",
     }
