@@ -24,6 +24,8 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline bool mult64(int64_t v) { return v > 0 && (v % 64) == 0; }
 inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 inline bool fits_int(int64_t v) { return v < ((int64_t)1 << 31); }
+// V:N:M shapes that are built: V = 64 rows, N = 2, M = 8 (fused step, fastest kernels) or 16 / 32 / 64 columns
+inline bool vnm_ok(int V, int M) { return V == 64 && (M == 8 || M == 16 || M == 32 || M == 64); }
 
 #define REQUIRE(cond, code, msg) do { if (!(cond)) return fail(code, "%s", msg); } while (0)
 #define LAUNCH(expr, where) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return hipfail(e_, where); } while (0)
@@ -119,11 +121,13 @@ int sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, int V, int M, 
                         uint8_t* colidx, void* stream) {
     REQUIRE(y1 && vals && meta && colidx, SFFN_EINVAL, "sqrelu_vnm_compress: null pointer");
     REQUIRE(mult64(T) && mult64(F), SFFN_EINVAL, "sqrelu_vnm_compress: T and F must be positive multiples of 64");
-    REQUIRE(V == 64 && M == 8, SFFN_EUNSUPPORTED, "sqrelu_vnm_compress: only V=64, M=8 is built");
+    REQUIRE(vnm_ok(V, M), SFFN_EUNSUPPORTED, "sqrelu_vnm_compress: only V=64 with M in {8, 16, 32, 64} is built");
+    REQUIRE(F % (2 * M) == 0, SFFN_EINVAL, "sqrelu_vnm_compress: F must be a multiple of 2 M");
     REQUIRE(aligned16(y1) && aligned16(vals) && aligned16(meta) && aligned16(colidx), SFFN_EINVAL,
             "sqrelu_vnm_compress: pointers must be 16-byte aligned");
     REQUIRE(fits_int(T) && fits_int(F) && T / 64 < 65536, SFFN_EUNSUPPORTED, "sqrelu_vnm_compress: T too large");
-    LAUNCH(launch_sqrelu_vnm_compress(y1, T, F, vals, meta, colidx, (hipStream_t)stream), "sqrelu_vnm_compress");
+    if (M == 8) LAUNCH(launch_sqrelu_vnm_compress(y1, T, F, vals, meta, colidx, (hipStream_t)stream), "sqrelu_vnm_compress");
+    else        LAUNCH(launch_sqrelu_vnm_compress_m(y1, T, F, M, vals, meta, colidx, (hipStream_t)stream), "sqrelu_vnm_compress");
     return SFFN_OK;
 }
 
@@ -153,7 +157,8 @@ int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_col
              size_t ws_bytes, void* stream) {
     REQUIRE(a_vals && a_meta && a_colidx && Wd && out, SFFN_EINVAL, "vnm_spmm: null pointer");
     REQUIRE(mult64(T) && mult64(N) && mult64(Kfull), SFFN_EINVAL, "vnm_spmm: T, N, Kfull must be positive multiples of 64");
-    REQUIRE(V == 64 && M == 8, SFFN_EUNSUPPORTED, "vnm_spmm: only V=64, M=8 is built");
+    REQUIRE(vnm_ok(V, M), SFFN_EUNSUPPORTED, "vnm_spmm: only V=64 with M in {8, 16, 32, 64} is built");
+    REQUIRE(Kfull % (2 * M) == 0, SFFN_EINVAL, "vnm_spmm: Kfull must be a multiple of 2 M");
     REQUIRE(w_kmajor == 0 || w_kmajor == 1, SFFN_EINVAL, "vnm_spmm: w_kmajor must be 0 or 1");
     REQUIRE(ldw >= (w_kmajor ? N : Kfull) && ldw % 8 == 0, SFFN_EINVAL, "vnm_spmm: ldw too small or not a multiple of 8");
     REQUIRE(w_kmajor == 1 || ldw == Kfull, SFFN_EUNSUPPORTED, "vnm_spmm: a padded row stride needs w_kmajor=1");
@@ -167,7 +172,8 @@ int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_col
     uint16_t* v24 = (uint16_t*)ws;
     uint8_t* m24 = ws + up256((size_t)T * Kfull);
     const uint16_t* W = Wd;
-    LAUNCH(launch_vnm_to_24(a_vals, a_meta, a_colidx, T, Kfull, v24, m24, s), "vnm_spmm/to24");
+    if (M == 8) LAUNCH(launch_vnm_to_24(a_vals, a_meta, a_colidx, T, Kfull, v24, m24, s), "vnm_spmm/to24");
+    else        LAUNCH(launch_vnm_to_24_m(a_vals, a_meta, a_colidx, T, Kfull, M, v24, m24, s), "vnm_spmm/to24");
     if (w_kmajor) {
         uint16_t* wt = (uint16_t*)(m24 + up256((size_t)T * Kfull / 8));
         LAUNCH(launch_transpose(Wd, Kfull, N, ldw, wt, 0, nullptr, s), "vnm_spmm/transpose");
@@ -181,11 +187,13 @@ int dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, co
                 int V, int M, uint16_t* dvals, void* stream) {
     REQUIRE(dy2 && y1 && meta && colidx && dvals, SFFN_EINVAL, "dsqrelu_vnm: null pointer");
     REQUIRE(mult64(T) && mult64(F), SFFN_EINVAL, "dsqrelu_vnm: T and F must be positive multiples of 64");
-    REQUIRE(V == 64 && M == 8, SFFN_EUNSUPPORTED, "dsqrelu_vnm: only V=64, M=8 is built");
+    REQUIRE(vnm_ok(V, M), SFFN_EUNSUPPORTED, "dsqrelu_vnm: only V=64 with M in {8, 16, 32, 64} is built");
+    REQUIRE(F % (2 * M) == 0, SFFN_EINVAL, "dsqrelu_vnm: F must be a multiple of 2 M");
     REQUIRE(aligned16(dy2) && aligned16(y1) && aligned16(meta) && aligned16(colidx) && aligned16(dvals), SFFN_EINVAL,
             "dsqrelu_vnm: pointers must be 16-byte aligned");
     REQUIRE(fits_int(T) && fits_int(F) && T < 65536, SFFN_EUNSUPPORTED, "dsqrelu_vnm: T must be below 65536");
-    LAUNCH(launch_dsqrelu_vnm(dy2, y1, meta, colidx, T, F, dvals, (hipStream_t)stream), "dsqrelu_vnm");
+    if (M == 8) LAUNCH(launch_dsqrelu_vnm(dy2, y1, meta, colidx, T, F, dvals, (hipStream_t)stream), "dsqrelu_vnm");
+    else        LAUNCH(launch_dsqrelu_vnm_m(dy2, y1, meta, colidx, T, F, M, dvals, (hipStream_t)stream), "dsqrelu_vnm");
     return SFFN_OK;
 }
 
@@ -194,7 +202,8 @@ int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_co
               void* stream) {
     REQUIRE(a_vals && a_meta && a_colidx && G && out, SFFN_EINVAL, "vnm_wgrad: null pointer");
     REQUIRE(mult64(T) && mult64(N) && mult64(F), SFFN_EINVAL, "vnm_wgrad: T, F, N must be positive multiples of 64");
-    REQUIRE(V == 64 && M == 8, SFFN_EUNSUPPORTED, "vnm_wgrad: only V=64, M=8 is built");
+    REQUIRE(vnm_ok(V, M), SFFN_EUNSUPPORTED, "vnm_wgrad: only V=64 with M in {8, 16, 32, 64} is built");
+    REQUIRE(F % (2 * M) == 0, SFFN_EINVAL, "vnm_wgrad: F must be a multiple of 2 M");
     REQUIRE(out_f_major == 0 || out_f_major == 1, SFFN_EINVAL, "vnm_wgrad: out_f_major must be 0 or 1");
     REQUIRE(aligned16(a_vals) && aligned16(a_meta) && aligned16(a_colidx) && aligned16(G) && aligned16(out) && aligned16(workspace),
             SFFN_EINVAL, "vnm_wgrad: pointers must be 16-byte aligned");
@@ -204,7 +213,8 @@ int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_co
     hipStream_t s = (hipStream_t)stream;
     uint16_t* at = (uint16_t*)workspace;
     uint16_t* gt = (uint16_t*)((unsigned char*)workspace + up256((size_t)F * T * 2));
-    LAUNCH(launch_vnm_expand_t(a_vals, a_meta, a_colidx, T, F, at, 0, s), "vnm_wgrad/expand");
+    if (M == 8) LAUNCH(launch_vnm_expand_t(a_vals, a_meta, a_colidx, T, F, at, 0, s), "vnm_wgrad/expand");
+    else        LAUNCH(launch_vnm_expand_t_m(a_vals, a_meta, a_colidx, T, F, M, at, s), "vnm_wgrad/expand");
     LAUNCH(launch_transpose(G, T, N, N, gt, 0, nullptr, s), "vnm_wgrad/transpose");
     // C[i=f][j=n]; out_f_major: out[f*N + n] (j contiguous) else out[n*F + f] (i contiguous)
     if (out_f_major) LAUNCH(launch_gemm_nt(0, at, nullptr, gt, nullptr, F, N, T, 0, out, N, s), "vnm_wgrad/gemm");

@@ -52,6 +52,15 @@ hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uin
 // batch > 1 (trans = 1 only): `batch` matrices of the same shape, consecutive in every argument.
 hipError_t launch_prune24_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
                                uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream, int batch = 1);
+// Wider blocks, M in {16, 32, 64} (vnm_general.hip): same operations and packed layout as the M = 8 kernels.
+hipError_t launch_sqrelu_vnm_compress_m(const uint16_t* y1, int64_t T, int64_t F, int M, uint16_t* vals, uint8_t* meta, uint8_t* colidx,
+                                        hipStream_t s);
+hipError_t launch_dsqrelu_vnm_m(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
+                                int M, uint16_t* dvals, hipStream_t s);
+hipError_t launch_vnm_to_24_m(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F, int M,
+                              uint16_t* vals24, uint8_t* meta24, hipStream_t s);
+hipError_t launch_vnm_expand_t_m(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F, int M,
+                                 uint16_t* out, hipStream_t s);
 hipError_t launch_vnm_to_24(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
                             uint16_t* vals24, uint8_t* meta24, hipStream_t s);
 hipError_t launch_vnm_expand_t(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,

@@ -50,7 +50,9 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     assert lib.prune24_compress(fake, 64, 64, 64, 0, 7, fake, fake, None) == -1
     assert lib.prune24_compress(odd, 64, 64, 64, 0, 0, fake, fake, None) == -1
     assert b"aligned" in lib.sffn_last_error()
-    assert lib.sqrelu_vnm_compress(fake, 64, 64, 64, 16, fake, fake, fake, None) == -2      # M = 16 not built
+    assert lib.sqrelu_vnm_compress(fake, 64, 64, 64, 12, fake, fake, fake, None) == -2      # M = 12 is not a built block width
+    assert lib.sqrelu_vnm_compress(fake, 64, 64, 32, 8, fake, fake, fake, None) == -2       # V = 32 neither
+    assert lib.sqrelu_vnm_compress(fake, 64, 64, 64, 64, fake, fake, fake, None) == -1      # F must be a multiple of 2 M
     assert lib.sqrelu_vnm_compress(fake, 63, 64, 64, 8, fake, fake, fake, None) == -1
     assert lib.spmm24_fwd(fake, fake, fake, None, 64, 64, 65, fake, None) == -1
     assert lib.spmm24_dgrad(fake, fake, None, 64, 64, 64, fake, None) == -1

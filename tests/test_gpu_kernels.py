@@ -300,3 +300,48 @@ def test_grouped_step_empty_and_single_block_experts():
         sv = step.saved()
         for k in ("y2_vals", "y2_meta", "colidx", "dy1_vals", "y1"):
             assert np.array_equal(se[k], to_bits(sv[k])), k
+
+
+# ---- wider V:N:M blocks (Table 5 of the paper: M = 16, 32, 64; density 2 / M) -------------------------------------
+@pytest.mark.parametrize("M", [16, 32, 64])
+@pytest.mark.parametrize("T,F", [(64, 256), (192, 1152), (256, 1024)])
+def test_sqrelu_vnm_compress_wide_blocks(T, F, M):
+    rng = np.random.default_rng(T + F + M)
+    y1 = _y1_like(rng, T, F, 0.5)
+    y1[:64, 0:M] = 0xBF80                         # dead block: all scores zero, ties go to the lowest columns
+    y1[:64, M:2 * M] = 0x3F80                     # fully tied block
+    y1[:64, 2 * M:3 * M] = 0x4580                 # 4096^2 = 2^24: ordered fp32 sums saturate
+    y1[1:64, 2 * M + 1] = 0x3F80
+    y1[0, 2 * M + 2] = 0x4581
+    vals, meta, colidx = sffn.sqrelu_vnm_compress(to_dev(y1), 64, M)
+    rv, rm, rc = oracle.sqrelu_vnm_compress(y1, 64, M)
+    assert np.array_equal(to_bits(colidx), rc)
+    assert np.array_equal(to_bits(meta), rm)
+    assert np.array_equal(to_bits(vals), rv)
+    assert rv.shape == (T, 2 * F // M) and rm.shape == (T, F // (2 * M)) and rc.shape == (T // 64, F // M, 4)
+
+
+@pytest.mark.parametrize("M", [16, 32, 64])
+def test_wide_block_consumers(M):
+    """eq. (6) bit-exact, eqs. (3), (7), (5), (8) within the GEMM tolerance, on V:2:M operands."""
+    T, F, D = 192, 640, 320
+    rng = np.random.default_rng(100 + M)
+    y1 = _y1_like(rng, T, F, 0.5)
+    dy2 = rnd_bits(rng, (T, F))
+    av, am, ac = oracle.sqrelu_vnm_compress(y1, 64, M)
+    dav, dam, dac = to_dev(av), to_dev(am), to_dev(ac)
+    dvals = sffn.dsqrelu_vnm(to_dev(dy2), to_dev(y1), dam, dac, 64, M)
+    assert np.array_equal(to_bits(dvals), oracle.dsqrelu_vnm(dy2, y1, am, ac, 64, M))
+    W2 = rnd_bits(rng, (D, F), 0.02)
+    W1 = rnd_bits(rng, (F, D), 0.02)
+    G = rnd_bits(rng, (T, D))
+    assert_gemm_close(to_bits(sffn.vnm_spmm(dav, dam, dac, to_dev(W2), 0, 64, M)), oracle.vnm_spmm(av, am, ac, W2, 0, 64, M), "y3")
+    assert_gemm_close(to_bits(sffn.vnm_spmm(dav, dam, dac, to_dev(W1), 1, 64, M)), oracle.vnm_spmm(av, am, ac, W1, 1, 64, M), "dX")
+    assert_gemm_close(to_bits(sffn.vnm_wgrad(dav, dam, dac, to_dev(G), 1, 64, M)), oracle.vnm_wgrad(av, am, ac, G, 1, 64, M), "dW1")
+    assert_gemm_close(to_bits(sffn.vnm_wgrad(dav, dam, dac, to_dev(G), 0, 64, M)), oracle.vnm_wgrad(av, am, ac, G, 0, 64, M), "dW2")
+    # small integers: the contractions must then be exact, which pins the 2:4 re-expression of the blocks bit for bit
+    yi = bf16_bits_from_f32(rng.integers(-3, 4, size=(T, F)).astype(np.float32))
+    Wi = bf16_bits_from_f32(rng.integers(-2, 3, size=(D, F)).astype(np.float32))
+    iv, im, ic = oracle.sqrelu_vnm_compress(yi, 64, M)
+    got = to_bits(sffn.vnm_spmm(to_dev(iv), to_dev(im), to_dev(ic), to_dev(Wi), 0, 64, M))
+    assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.vnm_spmm(iv, im, ic, Wi, 0, 64, M)))
