@@ -13,7 +13,8 @@
  *   - Return value: SFFN_OK, or a negative code with nothing enqueued for SFFN_EINVAL /
  *     SFFN_EUNSUPPORTED / SFFN_EWORKSPACE.  sffn_last_error() gives a thread-local text.
  *   - Shape rules: T % 64 == 0, D % 64 == 0, F % 64 == 0 (R, K, N below follow the same
- *     rule); base pointers 16-byte aligned.  V must be 64 and M must be 8.
+ *     rule); base pointers 16-byte aligned.  V must be 64; M is 8, 16, 32 or 64 (Table 5 of the paper) and the
+ *     compressed axis a multiple of 2 M.
  *   - Rounding: products accumulate in fp32 on the matrix cores; every stored bf16 is one
  *     round-to-nearest-even of an fp32 value.
  *
@@ -23,11 +24,12 @@
  *         bf16 pattern with the sign cleared, compared as an integer), at positions p0 < p1.
  *         vals[r,2g] = S[r,4g+p0], vals[r,2g+1] = S[r,4g+p1]; nibble = p0 | p1<<2;
  *         meta[r,g/2] holds group 2j in bits 3:0 and group 2j+1 in bits 7:4.
- *   V:N:M (V=64, N=2, M=8) block (tb,g) = rows 64tb..64tb+63, columns 8g..8g+7.  Column
+ *   V:N:M (V=64, N=2; written out for M=8) block (tb,g) = rows 64tb..64tb+63, columns 8g..8g+7.  Column
  *         score = fp32 sum of |y2| over the 64 rows, added in ascending row order from +0.
  *         The four columns of largest score survive (ties to the lower column);
  *         colidx[tb,g,0..3] are their offsets in ascending order.  Per row those four
- *         entries form one 2:4 group packed as above: vals[t,2g..2g+1], meta[t,g/2].
+ *         entries form one 2:4 group packed as above: vals[t,2g..2g+1], meta[t,g/2].  Wider blocks (M = 16,
+ *         32, 64) are the same with M columns per block: vals [T, 2F/M], meta [T, F/(2M)], colidx [T/64, F/M, 4].
  */
 #ifndef SPARSEFFN_H
 #define SPARSEFFN_H
@@ -53,7 +55,7 @@ typedef struct sffn_cfg {
     int64_t D;      /* d_model */
     int64_t F;      /* d_ffn */
     int32_t V;      /* V:N:M block height, 64 */
-    int32_t M;      /* V:N:M block width, 8 */
+    int32_t M;      /* V:N:M block width: 8 (fused kernels), or 16 / 32 / 64 (unfused path, see ffn_sparse_step) */
     int32_t mode;   /* SFFN_MODE_HARD or SFFN_MODE_SOFT for both weight sparsifiers */
     int32_t flags;  /* SFFN_FLAG_* */
 } sffn_cfg;
@@ -131,7 +133,10 @@ int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_co
 
 /* Alg. 1 + Alg. 2, one call: X [T,D], W1 [F,D], W2 [D,F], b1 fp32 [F] or NULL, dY [T,D] ->
  * Y3 [T,D], dX [T,D], dW1 [F,D], dW2 [D,F]; intermediates land in `workspace` at the offsets of
- * sffn_workspace_layout().  Both weight matrices are re-pruned inside the call. */
+ * sffn_workspace_layout().  Both weight matrices are re-pruned inside the call.
+ * cfg->M = 16, 32 or 64: the same algorithm from the stand-alone kernels (the V:2:M activation is still a plain 2:4
+ * matrix over all F columns, so eqs. (3), (7) stay on the structured-sparse matrix cores); the dense y1 and dy2 are
+ * then always stored, y1_kept is not produced, and the packed activation tensors have the sizes given above. */
 int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, const uint16_t* W2,
                     const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
                     uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);

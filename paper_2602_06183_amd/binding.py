@@ -120,13 +120,13 @@ def _cfg(T, D, F, mode=MODE_HARD, V=64, M=8, flags=0):
     return _Cfg(T, D, F, V, M, mode, flags)
 
 
-def workspace_bytes(T, D, F, mode=MODE_HARD):
-    c = _cfg(T, D, F, mode)
+def workspace_bytes(T, D, F, mode=MODE_HARD, M=8):
+    c = _cfg(T, D, F, mode, M=M)
     return load().sffn_workspace_bytes(ctypes.byref(c))
 
 
-def workspace_layout(T, D, F, mode=MODE_HARD):
-    c, lay = _cfg(T, D, F, mode), _Layout()
+def workspace_layout(T, D, F, mode=MODE_HARD, M=8):
+    c, lay = _cfg(T, D, F, mode, M=M), _Layout()
     _check(load().sffn_workspace_layout(ctypes.byref(c), ctypes.byref(lay)))
     return {n: getattr(lay, n) for n, _ in _Layout._fields_}
 
@@ -197,12 +197,13 @@ def vnm_wgrad(a_vals, a_meta, a_colidx, G, out_f_major, V=64, M=8):
 class FfnStep:
     """Pre-allocated outputs and workspace for repeated ffn_sparse_step calls on one shape."""
 
-    def __init__(self, T, D, F, mode=MODE_HARD, device="cuda", keep_dense=False):
+    def __init__(self, T, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8):
         """keep_dense: also store the dense y1 and dy2 (SFFN_FLAG_KEEP_DENSE); otherwise only y1 at y2's kept
-        slots is saved for the backward pass."""
-        self.T, self.D, self.F, self.mode, self.keep_dense = T, D, F, mode, keep_dense
-        self.cfg = _cfg(T, D, F, mode, flags=FLAG_KEEP_DENSE if keep_dense else 0)
-        self.layout = workspace_layout(T, D, F, mode)
+        slots is saved for the backward pass.  M: V:N:M block width, 8 (fused kernels) or 16 / 32 / 64 (unfused
+        path that always stores y1 and dy2 and produces no y1_kept)."""
+        self.T, self.D, self.F, self.mode, self.keep_dense, self.M = T, D, F, mode, keep_dense, M
+        self.cfg = _cfg(T, D, F, mode, M=M, flags=FLAG_KEEP_DENSE if keep_dense else 0)
+        self.layout = workspace_layout(T, D, F, mode, M)
         self.ws = _u8((self.layout["total"],), device)
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
         self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
@@ -214,7 +215,7 @@ class FfnStep:
 
     def saved(self):
         """Views of the intermediates the step leaves in its workspace (Alg. 2 line 1 and friends)."""
-        T, D, F, L = self.T, self.D, self.F, self.layout
+        T, D, F, M, L = self.T, self.D, self.F, self.M, self.layout
 
         def view(off, shape, dtype):
             n = 1
@@ -223,12 +224,14 @@ class FfnStep:
             nbytes = n * (2 if dtype == torch.bfloat16 else 1)
             return self.ws[off:off + nbytes].view(dtype).view(shape)
 
-        return dict(w1_vals=view(L["w1_vals"], (F, D // 2), torch.bfloat16), w1_meta=view(L["w1_meta"], (F, D // 8), torch.uint8),
-                    w2t_vals=view(L["w2t_vals"], (F, D // 2), torch.bfloat16), w2t_meta=view(L["w2t_meta"], (F, D // 8), torch.uint8),
-                    y1=view(L["y1"], (T, F), torch.bfloat16), y2_vals=view(L["y2_vals"], (T, F // 4), torch.bfloat16),
-                    y2_meta=view(L["y2_meta"], (T, F // 16), torch.uint8), colidx=view(L["colidx"], (T // 64, F // 8, 4), torch.uint8),
-                    dy2=view(L["dy2"], (T, F), torch.bfloat16), dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16),
-                    y1_kept=view(L["y1_kept"], (T, F // 4), torch.bfloat16))
+        out = dict(w1_vals=view(L["w1_vals"], (F, D // 2), torch.bfloat16), w1_meta=view(L["w1_meta"], (F, D // 8), torch.uint8),
+                   w2t_vals=view(L["w2t_vals"], (F, D // 2), torch.bfloat16), w2t_meta=view(L["w2t_meta"], (F, D // 8), torch.uint8),
+                   y1=view(L["y1"], (T, F), torch.bfloat16), y2_vals=view(L["y2_vals"], (T, 2 * F // M), torch.bfloat16),
+                   y2_meta=view(L["y2_meta"], (T, F // (2 * M)), torch.uint8), colidx=view(L["colidx"], (T // 64, F // M, 4), torch.uint8),
+                   dy2=view(L["dy2"], (T, F), torch.bfloat16), dy1_vals=view(L["dy1_vals"], (T, 2 * F // M), torch.bfloat16))
+        if M == 8:
+            out["y1_kept"] = view(L["y1_kept"], (T, F // 4), torch.bfloat16)
+        return out
 
 
 class FfnStepGrouped:
@@ -272,9 +275,9 @@ class FfnStepGrouped:
                     y1_kept=view(L["y1_kept"], (T, F // 4), torch.bfloat16))
 
 
-def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD, keep_dense=True):
+def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD, keep_dense=True, M=8):
     T, D = X.shape
     F = W1.shape[0]
-    step = FfnStep(T, D, F, mode, X.device, keep_dense)
+    step = FfnStep(T, D, F, mode, X.device, keep_dense, M)
     out = step(X, W1, W2, b1, dY)
     return out, step

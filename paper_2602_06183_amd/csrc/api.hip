@@ -50,6 +50,8 @@ struct FullLayout {
 // E = number of experts (1 for the plain step): every weight-shaped tensor holds E matrices back to back.
 bool make_layout(const sffn_cfg* c, FullLayout* L, int n_experts = 1) {
     if (!c || !mult64(c->T) || !mult64(c->D) || !mult64(c->F) || n_experts < 1) return false;
+    const size_t M = (c->M == 16 || c->M == 32 || c->M == 64) ? (size_t)c->M : 8;   // wider blocks: smaller packed tensors, unfused path
+    if (c->F % (2 * M) != 0) return false;
     const size_t T = c->T, D = c->D, F = (size_t)c->F * n_experts;   // F only sizes weight-shaped tensors below ...
     const size_t TF = T * (size_t)c->F;                               // ... token x hidden tensors use TF
     size_t off = 0;
@@ -57,17 +59,17 @@ bool make_layout(const sffn_cfg* c, FullLayout* L, int n_experts = 1) {
     L->pub.w1_vals = take(F * D);          L->pub.w1_meta = take(F * D / 8);
     L->pub.w2t_vals = take(F * D);         L->pub.w2t_meta = take(F * D / 8);
     L->pub.y1 = take(TF * 2);
-    L->pub.y2_vals = take(TF / 2);      L->pub.y2_meta = take(TF / 16);   L->pub.colidx = take(TF / 64 / 8 * 4);
+    L->pub.y2_vals = take(TF * 4 / M);  L->pub.y2_meta = take(TF / (2 * M));   L->pub.colidx = take(TF / 64 / M * 4);
     L->pub.dy2 = take(TF * 2);
-    L->pub.dy1_vals = take(TF / 2);
-    L->pub.y1_kept = take(TF / 2);
+    L->pub.dy1_vals = take(TF * 4 / M);
+    L->pub.y1_kept = take(M == 8 ? TF / 2 : 0);
     L->w1_vblk = take(F * D);              L->w1_mblk = take(F * D / 8);
     L->w2t_vblk = take(F * D);             L->w2t_mblk = take(F * D / 8);
     L->x_blk = take(T * D * 2);            L->xt_blk = take(D * T * 2);
     L->dy_blk = take(T * D * 2);           L->dyt_blk = take(D * T * 2);
     L->w2_blk = take(D * F * 2);           L->w1t_blk = take(D * F * 2);
     L->a24_vblk = take(TF);             L->a24_mblk = take(TF / 8);
-    L->at_blk = take(TF);               // transposed activation, compacted to the kept hidden units: [F / 2, T]
+    L->at_blk = take(M == 8 ? TF : 2 * TF);   // M = 8: transposed activation compacted to the kept hidden units [F / 2, T]; wider: dense [F, T]
     L->kmask = take(TF / 64 / 8);       // kept-column bit mask per (64-token block, group of 8 hidden units)
     L->total = off;
     L->pub.total = off;
@@ -230,8 +232,9 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     REQUIRE(cfg && X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_sparse_step: null pointer");
     FullLayout L;
     REQUIRE(n_experts >= 1 && n_experts <= GemmGroup::kMaxExperts, SFFN_EINVAL, "ffn_sparse_step_grouped: n_experts must be in 1..64");
-    REQUIRE(make_layout(cfg, &L, n_experts), SFFN_EINVAL, "ffn_sparse_step: T, D, F must be positive multiples of 64");
-    REQUIRE(cfg->V == 64 && cfg->M == 8, SFFN_EUNSUPPORTED, "ffn_sparse_step: only V=64, M=8 is built");
+    REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "ffn_sparse_step: only V=64 with M in {8, 16, 32, 64} is built");
+    REQUIRE(make_layout(cfg, &L, n_experts), SFFN_EINVAL, "ffn_sparse_step: T, D, F must be positive multiples of 64 and F a multiple of 2 M");
+    REQUIRE(cfg->M == 8 || (seg == nullptr && n_experts == 1), SFFN_EUNSUPPORTED, "ffn_sparse_step_grouped: only M=8 is built");
     REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_sparse_step: unknown mode");
     REQUIRE(aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(b1) && aligned16(dY) && aligned16(Y3) && aligned16(dX) &&
                 aligned16(dW1) && aligned16(dW2) && aligned16(workspace),
@@ -268,6 +271,35 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     uint8_t* kmask = ws + L.kmask;
     uint16_t* ykept = (uint16_t*)(ws + L.pub.y1_kept);
     const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
+    if (cfg->M != 8) {
+        // Wider blocks (Table 5): the same Alg. 1 / Alg. 2 from the stand-alone kernels on row-major operands; the
+        // V:2:M activation is still a valid plain 2:4 matrix over all F columns, so eqs. (3), (7) stay on smfmac.
+        // The dense y1 and dy2 are always stored (they are what eq. (6) reads), y1_kept is not produced.
+        const int M = cfg->M;
+        if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
+        uint16_t* at = atb;                              // dense [F, T]
+        uint16_t* tr = xtb;                              // transposes: dY.T, W1.T, X.T in turn ([D, T] or [D, F])
+        uint16_t* w1t = w1tb;
+        STAGE(launch_prune24(W1, F, D, D, 0, cfg->mode, w1v, w1m, s), "step/prune24(W1)");
+        STAGE(launch_gemm_nt(1, w1v, w1m, X, b1, F, T, D, 1, y1, F, s), "step/y1");                                   // eq. (1)
+        STAGE(launch_sqrelu_vnm_compress_m(y1, T, F, M, y2v, y2m, cix, s), "step/sqrelu_vnm_compress");               // eq. (2), Section 2.3
+        STAGE(launch_vnm_to_24_m(y2v, y2m, cix, T, F, M, a24v, a24m, s), "step/to24(y2)");
+        STAGE(launch_gemm_nt(1, a24v, a24m, W2, nullptr, T, D, F, 0, Y3, D, s), "step/y3");                           // eq. (3)
+        STAGE(launch_prune24(W2, F, D, F, 1, cfg->mode, w2v, w2m, s), "step/prune24(W2.T)");
+        STAGE(launch_gemm_nt(1, w2v, w2m, dY, nullptr, F, T, D, 1, dy2, F, s), "step/dy2");                           // eq. (4)
+        STAGE(launch_vnm_expand_t_m(y2v, y2m, cix, T, F, M, at, s), "step/expand(y2)");
+        STAGE(launch_transpose(dY, T, D, D, tr, 0, nullptr, s), "step/dY.T");
+        STAGE(launch_gemm_nt(0, at, nullptr, tr, nullptr, F, D, T, 1, dW2, F, s), "step/dW2");                        // eq. (5)
+        STAGE(launch_dsqrelu_vnm_m(dy2, y1, y2m, cix, T, F, M, dy1v, s), "step/dsqrelu_vnm");                         // eq. (6)
+        STAGE(launch_vnm_to_24_m(dy1v, y2m, cix, T, F, M, a24v, a24m, s), "step/to24(dy1)");
+        STAGE(launch_transpose(W1, F, D, D, w1t, 0, nullptr, s), "step/W1.T");
+        STAGE(launch_gemm_nt(1, a24v, a24m, w1t, nullptr, T, D, F, 0, dX, D, s), "step/dX");                          // eq. (7)
+        STAGE(launch_vnm_expand_t_m(dy1v, y2m, cix, T, F, M, at, s), "step/expand(dy1)");
+        STAGE(launch_transpose(X, T, D, D, tr, 0, nullptr, s), "step/X.T");
+        STAGE(launch_gemm_nt(0, at, nullptr, tr, nullptr, F, D, T, 0, dW1, D, s), "step/dW1");                        // eq. (8)
+        (void)keep_dense;
+        return SFFN_OK;
+    }
     // the three ways a token segment meets its expert's weights (see GemmGroup)
     GemmGroup g_packed = g, g_dense = g, g_wgrad = g;
     g_packed.role = 1; g_packed.a_stride = F * D / 2; g_packed.m_stride = F * D / 8; g_packed.bias_stride = F;

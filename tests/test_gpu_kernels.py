@@ -183,6 +183,24 @@ def _check_step_against_oracle(inp, s, outs, mode):
     assert_gemm_close(outs["dW1"], oracle.vnm_wgrad(dv, ym, yc, inp["X"], 1), "dW1")
 
 
+def _check_wide_step_against_oracle(inp, s, outs, mode, M):
+    """The same teacher-forced chain for V:2:M blocks wider than 8 (no y1_kept in that path)."""
+    rv, rm = oracle.prune24_compress(inp["W1"], mode)
+    assert np.array_equal(s["w1_vals"], rv) and np.array_equal(s["w1_meta"], rm)
+    assert_gemm_close(s["y1"], oracle.spmm24(inp["X"], rv, rm, inp["b1"]), "y1")
+    yv, ym, yc = oracle.sqrelu_vnm_compress(s["y1"], 64, M)
+    assert np.array_equal(s["colidx"], yc) and np.array_equal(s["y2_meta"], ym) and np.array_equal(s["y2_vals"], yv)
+    assert_gemm_close(outs["Y3"], oracle.vnm_spmm(yv, ym, yc, inp["W2"], 0, 64, M), "y3")
+    rv2, rm2 = oracle.prune24_compress(np.ascontiguousarray(inp["W2"].T), mode)
+    assert np.array_equal(s["w2t_vals"], rv2) and np.array_equal(s["w2t_meta"], rm2)
+    assert_gemm_close(s["dy2"], oracle.spmm24(inp["dY"], rv2, rm2, None), "dy2")
+    dv = oracle.dsqrelu_vnm(s["dy2"], s["y1"], ym, yc, 64, M)
+    assert np.array_equal(s["dy1_vals"], dv)
+    assert_gemm_close(outs["dW2"], oracle.vnm_wgrad(yv, ym, yc, inp["dY"], 0, 64, M), "dW2")
+    assert_gemm_close(outs["dX"], oracle.vnm_spmm(dv, ym, yc, inp["W1"], 1, 64, M), "dX")
+    assert_gemm_close(outs["dW1"], oracle.vnm_wgrad(dv, ym, yc, inp["X"], 1, 64, M), "dW1")
+
+
 def _teacher_forced_step_check(T, D, F, mode, seed):
     inp = make_ffn_inputs(T, D, F, seed=seed)
     dev = {k: to_dev(v) for k, v in inp.items()}
@@ -345,3 +363,18 @@ def test_wide_block_consumers(M):
     iv, im, ic = oracle.sqrelu_vnm_compress(yi, 64, M)
     got = to_bits(sffn.vnm_spmm(to_dev(iv), to_dev(im), to_dev(ic), to_dev(Wi), 0, 64, M))
     assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.vnm_spmm(iv, im, ic, Wi, 0, 64, M)))
+
+
+@pytest.mark.parametrize("M,mode", [(16, sffn.MODE_HARD), (32, sffn.MODE_SOFT), (64, sffn.MODE_HARD)])
+def test_ffn_sparse_step_wide_blocks(M, mode):
+    """ffn_sparse_step with V:2:M blocks of 16 / 32 / 64 columns, teacher-forced against the oracle stage by stage."""
+    T, D, F = 320, 192, 640
+    inp = make_ffn_inputs(T, D, F, seed=7, zero_fraction=0.75)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    (Y3, dX, dW1, dW2), step = sffn.ffn_sparse_step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"], mode, M=M)
+    torch.cuda.synchronize()
+    s = {k: to_bits(v) for k, v in step.saved().items()}
+    outs = dict(Y3=to_bits(Y3), dX=to_bits(dX), dW1=to_bits(dW1), dW2=to_bits(dW2))
+    _check_wide_step_against_oracle(inp, s, outs, mode, M)
+    density = np.mean(oracle.vnm_decompress(s["y2_vals"], s["y2_meta"], s["colidx"], 64, M) != 0)
+    assert density <= 2.0 / M + 1e-9                       # Table 5: sparsity at least 1 - N / M
