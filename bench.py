@@ -19,22 +19,23 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_flops(stage, T, D, F):
+def algorithmic_flops(stage, T, D, F, M=8):
     """Multiply-adds the method itself needs (non-zero products), times two, per launch."""
     tdf = float(T) * D * F
-    return {"step/y1+sqrelu_vnm_compress": tdf, "step/dy2+dsqrelu_vnm": tdf,                      # 2:4 weights: half of K survives
-            "step/y3": 0.5 * tdf, "step/dX": 0.5 * tdf,          # V:2:8 activations: a quarter survives
-            "step/dW2": 0.5 * tdf, "step/dW1": 0.5 * tdf}.get(stage)
+    act = 4.0 / M * tdf                                          # V:2:M activations: 2 of M survive (M = 8: a quarter)
+    return {"step/y1+sqrelu_vnm_compress": tdf, "step/dy2+dsqrelu_vnm": tdf, "step/y1": tdf, "step/dy2": tdf,   # 2:4 weights: half of K survives
+            "step/y3": act, "step/dX": act, "step/dW2": act, "step/dW1": act}.get(stage)
 
 
 def executed_flops(stage, T, D, F):
     """Flops the matrix cores are issued for (dense-equivalent of the instructions used)."""
     tdf = float(T) * D * F
-    return {"step/y1+sqrelu_vnm_compress": 2 * tdf, "step/dy2+dsqrelu_vnm": 2 * tdf, "step/y3": 2 * tdf, "step/dX": 2 * tdf,
-            "step/dW2": 2 * tdf, "step/dW1": 2 * tdf}.get(stage)
+    return {"step/y1+sqrelu_vnm_compress": 2 * tdf, "step/dy2+dsqrelu_vnm": 2 * tdf, "step/y1": 2 * tdf, "step/dy2": 2 * tdf,
+            "step/y3": 2 * tdf, "step/dX": 2 * tdf, "step/dW2": 2 * tdf, "step/dW1": 2 * tdf}.get(stage)
 
 
 KERNEL_OF_STAGE = {"step/y1+sqrelu_vnm_compress": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dy2+dsqrelu_vnm": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
+                   "step/y1": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dy2": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
                    "step/y3": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dX": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
                    "step/dW2": "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>", "step/dW1": "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>"}
 
@@ -47,6 +48,8 @@ def main():
     ap.add_argument("--workload", default="1b", help="tiny | 1b | 7b | 70b | moe_expert | moe (8 experts, 16384 tokens routed top-2, grouped launches)")
     ap.add_argument("--zero-fraction", type=float, default=0.90)
     ap.add_argument("--mode", default="hard", choices=["hard", "soft"])
+    ap.add_argument("--M", type=int, default=8, choices=[8, 16, 32, 64],
+                    help="V:2:M block width of the activation format (Table 5); 8 is the headline configuration, wider blocks run the unfused path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference kernel for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -62,6 +65,9 @@ def main():
     sffn.load()                     # fails loudly when the HIP library is missing
     mode = sffn.MODE_SOFT if args.mode == "soft" else sffn.MODE_HARD
     moe = args.workload == "moe"
+    M = args.M
+    if moe and M != 8:
+        sys.exit("bench.py: the grouped step is built for M = 8 only")
     if moe:
         _, D, F = CONFIGS["moe_expert"]
         inp = make_moe_inputs(16384, 8, 2, D, F, seed=0, zero_fraction=args.zero_fraction)
@@ -77,7 +83,7 @@ def main():
         return torch.from_numpy(a).cuda()
 
     X, W1, W2, b1, dY = (dev(inp[k]) for k in ("X", "W1", "W2", "b1", "dY"))
-    step = sffn.FfnStepGrouped(seg, D, F, mode) if moe else sffn.FfnStep(T, D, F, mode)
+    step = sffn.FfnStepGrouped(seg, D, F, mode) if moe else sffn.FfnStep(T, D, F, mode, M=M)
     flops = 12.0 * T * D * F
 
     # ---- dense bf16 FFN step on hipBLASLt (torch.matmul), same shapes, same process -------------
@@ -149,18 +155,20 @@ def main():
             acc[name] = acc.get(name, 0.0) + ms / nprof
     sffn.profile_enable(False)
     by_kernel = {}
+    if M != 8:      # the wide-block path contracts the expanded activation with the dense-operand variant of the tile kernel
+        KERNEL_OF_STAGE.update({"step/dW2": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>", "step/dW1": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>"})
     for name, ms in acc.items():
         k = KERNEL_OF_STAGE.get(name, name)
         by_kernel.setdefault(k, []).append((name, ms))
     dom_kernel = max(by_kernel, key=lambda k: sum(ms for _, ms in by_kernel[k]))
     launches = by_kernel[dom_kernel]
     avg_ms = sum(ms for _, ms in launches) / len(launches)
-    alg = sum(algorithmic_flops(n, T, D, F) or 0.0 for n, _ in launches) / len(launches)
+    alg = sum(algorithmic_flops(n, T, D, F, M) or 0.0 for n, _ in launches) / len(launches)
     exe = sum(executed_flops(n, T, D, F) or 0.0 for n, _ in launches) / len(launches)
     achieved = alg / (avg_ms * 1e-3) / 1e12
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and M == 8:
         traffic = json.load(open(tpath)).get(dom_kernel)
     roofline = {"bound": "mfma", "kernel": dom_kernel, "launches_per_step": len(launches), "avg_launch_ms": round(avg_ms, 4),
                 "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -193,7 +201,7 @@ def main():
     retained = None
     if not moe:
         del y2, dy2, dy1                                   # the dense baseline's buffers are no longer needed
-        chk = sffn.FfnStep(T, D, F, mode, keep_dense=True)
+        chk = sffn.FfnStep(T, D, F, mode, keep_dense=True, M=M)
         chk(X, W1, W2, b1, dY)
         sv = chk.saved()
         y2_all = torch.clamp_min(sv["y1"].float(), 0.0).square_().to(torch.bfloat16)        # eq. (2), rounded as the kernel does
@@ -230,8 +238,8 @@ def main():
         "config": {"workload": ("moe: 8 experts, 16384 tokens routed top-2 = %d token slots in segments %s (64-row aligned), d_model=%d, d_ff=%d per expert, "
                                 "2:4 weights (%s), V:N:M 64:2:8 SquaredReLU, zero fraction %.2f, seed 0; one grouped launch per stage"
                                 % (T, seg, D, F, args.mode, args.zero_fraction)) if moe else
-                               "%s: one FFN layer, T=%d tokens, d_model=%d, d_ff=%d, 2:4 weights (%s), V:N:M 64:2:8 SquaredReLU, zero fraction %.2f, seed 0"
-                               % (args.workload, T, D, F, args.mode, args.zero_fraction)},
+                               "%s: one FFN layer, T=%d tokens, d_model=%d, d_ff=%d, 2:4 weights (%s), V:N:M 64:2:%d SquaredReLU, zero fraction %.2f, seed 0"
+                               % (args.workload, T, D, F, args.mode, M, args.zero_fraction)},
         "frac_of_mfma_peak": round(value / MFMA_BF16_PEAK_TFLOPS, 4),
         "dense_ms_per_step": round(ms_dense, 4), "dense_tflops": round(flops / (ms_dense * 1e-3) / 1e12, 2),
         "dense_frac_of_mfma_peak": round(flops / (ms_dense * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
