@@ -196,6 +196,30 @@ def main():
         "hbm_peak GB/s": HBM_PEAK_GBS,
     }
 
+    # ---- the activation GEMM alone for every block width of Table 5, against the dense GEMM of the same shape
+    #      (Section 5.2.3's micro-benchmark): out[T, D] = y2v[T, F] @ W1[F, D], eq. (7)'s orientation ------------------
+    venom = None
+    if not moe:
+        def ms_of(fn, n=10):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            e1.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        dense_out = torch.empty((y1_one.shape[0], D), dtype=torch.bfloat16, device="cuda")
+        t_dense = ms_of(lambda: torch.mm(y1_one, w1_one, out=dense_out))
+        venom = {"shape": "[%d, %d] x [%d, %d]" % (y1_one.shape[0], F, F, D), "dense_ms": round(t_dense, 4)}
+        for m in (8, 16, 32, 64):
+            pack = sffn.sqrelu_vnm_compress(y1_one, 64, m)
+            t = ms_of(lambda: sffn.vnm_spmm(pack[0], pack[1], pack[2], w1_one, 1, 64, m))
+            venom["64:2:%d" % m] = {"ms": round(t, 4), "speedup_vs_dense": round(t_dense / t, 3)}
+        del dense_out
+
     # ---- how much of the activation's L1 mass the V:N:M format keeps (sum of kept y2 / sum of all y2): one extra,
     #      untimed step that also stores the dense y1; plain torch reductions, measurement only ------------------
     retained = None
@@ -247,6 +271,7 @@ def main():
         "second_pass": {"ms_per_step": round(ms_sparse2, 4), "dense_ms_per_step": round(ms_dense2, 4)},
         "stage_ms": {k: round(v, 4) for k, v in acc.items()},
         "standalone_kernels": kernels,
+        "venom_gemm_microbench": venom,
         "retained_l1_fraction": retained, "relu_zero_fraction": zero_frac,
         "roofline": roofline, "cpu_baseline": cpu,
         "paper_context": "paper reports 1.4-1.5x for 2:4 GEMMs and 1.4-1.7x end-to-end on NVIDIA sparse tensor cores (Sections 1, 5.2.3); context, not a target",

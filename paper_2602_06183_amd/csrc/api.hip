@@ -98,7 +98,8 @@ int sffn_workspace_layout(const sffn_cfg* cfg, sffn_ws_layout* out) {
 
 size_t sffn_vnm_spmm_workspace_bytes(int64_t T, int64_t N, int64_t Kfull, int w_kmajor) {
     if (!mult64(T) || !mult64(N) || !mult64(Kfull)) return 0;
-    return up256((size_t)T * Kfull) + up256((size_t)T * Kfull / 8) + (w_kmajor ? up256((size_t)N * Kfull * 2) : 0);
+    (void)w_kmajor;         // either orientation may need the other one's copy of Wd (plain-2:4 route: [N, Kfull]; gathered route: [Kfull, N])
+    return up256((size_t)T * Kfull) + up256((size_t)T * Kfull / 8) + up256((size_t)N * Kfull * 2);
 }
 
 size_t sffn_vnm_wgrad_workspace_bytes(int64_t T, int64_t F, int64_t N) {
@@ -174,10 +175,21 @@ int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_col
     uint16_t* v24 = (uint16_t*)ws;
     uint8_t* m24 = ws + up256((size_t)T * Kfull);
     const uint16_t* W = Wd;
+    uint16_t* wcopy = (uint16_t*)(m24 + up256((size_t)T * Kfull / 8));
+    if (vnm_spmm_gather_ok(T, N, Kfull, M) && Kfull * (w_kmajor ? ldw : N) * 2 < ((int64_t)1 << 32)) {
+        // M >= 16: contract over the 4 Kfull / M kept columns only, gathering their rows of the [Kfull, N] operand
+        int64_t ldk = ldw;
+        if (!w_kmajor) {
+            LAUNCH(launch_transpose(Wd, N, Kfull, ldw, wcopy, 0, nullptr, s), "vnm_spmm/transpose");
+            W = wcopy; ldk = N;
+        }
+        LAUNCH(launch_vnm_spmm_gather(a_vals, a_meta, a_colidx, W, ldk, T, N, Kfull, M, out, N, s), "vnm_spmm/gather");
+        return SFFN_OK;
+    }
     if (M == 8) LAUNCH(launch_vnm_to_24(a_vals, a_meta, a_colidx, T, Kfull, v24, m24, s), "vnm_spmm/to24");
     else        LAUNCH(launch_vnm_to_24_m(a_vals, a_meta, a_colidx, T, Kfull, M, v24, m24, s), "vnm_spmm/to24");
     if (w_kmajor) {
-        uint16_t* wt = (uint16_t*)(m24 + up256((size_t)T * Kfull / 8));
+        uint16_t* wt = wcopy;
         LAUNCH(launch_transpose(Wd, Kfull, N, ldw, wt, 0, nullptr, s), "vnm_spmm/transpose");
         W = wt;
     }
@@ -283,17 +295,29 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
         STAGE(launch_prune24(W1, F, D, D, 0, cfg->mode, w1v, w1m, s), "step/prune24(W1)");
         STAGE(launch_gemm_nt(1, w1v, w1m, X, b1, F, T, D, 1, y1, F, s), "step/y1");                                   // eq. (1)
         STAGE(launch_sqrelu_vnm_compress_m(y1, T, F, M, y2v, y2m, cix, s), "step/sqrelu_vnm_compress");               // eq. (2), Section 2.3
-        STAGE(launch_vnm_to_24_m(y2v, y2m, cix, T, F, M, a24v, a24m, s), "step/to24(y2)");
-        STAGE(launch_gemm_nt(1, a24v, a24m, W2, nullptr, T, D, F, 0, Y3, D, s), "step/y3");                           // eq. (3)
+        // eqs. (3), (7): gather the kept rows of the dense operand (matrix work and traffic shrink with 4 / M); shapes the
+        // gathered kernel does not cover re-express the activation as plain 2:4 over all F columns instead
+        const bool gather = vnm_spmm_gather_ok(T, D, F, M) && F * D * 2 < ((int64_t)1 << 32);
+        if (gather) {
+            STAGE(launch_transpose(W2, D, F, F, w1t, 0, nullptr, s), "step/W2.T");
+            STAGE(launch_vnm_spmm_gather(y2v, y2m, cix, w1t, D, T, D, F, M, Y3, D, s), "step/y3");                    // eq. (3)
+        } else {
+            STAGE(launch_vnm_to_24_m(y2v, y2m, cix, T, F, M, a24v, a24m, s), "step/to24(y2)");
+            STAGE(launch_gemm_nt(1, a24v, a24m, W2, nullptr, T, D, F, 0, Y3, D, s), "step/y3");                       // eq. (3)
+        }
         STAGE(launch_prune24(W2, F, D, F, 1, cfg->mode, w2v, w2m, s), "step/prune24(W2.T)");
         STAGE(launch_gemm_nt(1, w2v, w2m, dY, nullptr, F, T, D, 1, dy2, F, s), "step/dy2");                           // eq. (4)
         STAGE(launch_vnm_expand_t_m(y2v, y2m, cix, T, F, M, at, s), "step/expand(y2)");
         STAGE(launch_transpose(dY, T, D, D, tr, 0, nullptr, s), "step/dY.T");
         STAGE(launch_gemm_nt(0, at, nullptr, tr, nullptr, F, D, T, 1, dW2, F, s), "step/dW2");                        // eq. (5)
         STAGE(launch_dsqrelu_vnm_m(dy2, y1, y2m, cix, T, F, M, dy1v, s), "step/dsqrelu_vnm");                         // eq. (6)
-        STAGE(launch_vnm_to_24_m(dy1v, y2m, cix, T, F, M, a24v, a24m, s), "step/to24(dy1)");
-        STAGE(launch_transpose(W1, F, D, D, w1t, 0, nullptr, s), "step/W1.T");
-        STAGE(launch_gemm_nt(1, a24v, a24m, w1t, nullptr, T, D, F, 0, dX, D, s), "step/dX");                          // eq. (7)
+        if (gather) {
+            STAGE(launch_vnm_spmm_gather(dy1v, y2m, cix, W1, D, T, D, F, M, dX, D, s), "step/dX");                    // eq. (7)
+        } else {
+            STAGE(launch_vnm_to_24_m(dy1v, y2m, cix, T, F, M, a24v, a24m, s), "step/to24(dy1)");
+            STAGE(launch_transpose(W1, F, D, D, w1t, 0, nullptr, s), "step/W1.T");
+            STAGE(launch_gemm_nt(1, a24v, a24m, w1t, nullptr, T, D, F, 0, dX, D, s), "step/dX");                      // eq. (7)
+        }
         STAGE(launch_vnm_expand_t_m(dy1v, y2m, cix, T, F, M, at, s), "step/expand(dy1)");
         STAGE(launch_transpose(X, T, D, D, tr, 0, nullptr, s), "step/X.T");
         STAGE(launch_gemm_nt(0, at, nullptr, tr, nullptr, F, D, T, 0, dW1, D, s), "step/dW1");                        // eq. (8)

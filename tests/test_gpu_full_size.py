@@ -151,3 +151,55 @@ def test_full_size_grouped_step():
             assert np.array_equal(full[4][e][r], rv) and np.array_equal(full[5][e][r], rm)
             rv, rm = oracle.prune24_compress(np.ascontiguousarray(m["W2"][e][:, r].T))
             assert np.array_equal(full[6][e][r], rv) and np.array_equal(full[7][e][r], rm)
+
+
+@pytest.mark.parametrize("M", [16, 64])
+def test_full_size_wide_block_step(M):
+    """Table 5's wider blocks at the 1B shape, as bench.py --M times it: eqs. (3), (7) on the gathered-row kernel.
+    Compressors bit-exact on sampled token blocks, GEMM outputs on sampled rows / column blocks, teacher-forced."""
+    T, D, F = CONFIGS["1b"]
+    inp = make_ffn_inputs(T, D, F, seed=0)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    step = sffn.FfnStep(T, D, F, sffn.MODE_HARD, M=M)
+    outs = step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    torch.cuda.synchronize()
+    Y3, dX, dW1, dW2 = (to_bits(t) for t in outs)
+    sv = {k: to_bits(v) for k, v in step.saved().items()}
+    y1, dy2, yv, ym, yc, dv = (sv[k] for k in ("y1", "dy2", "y2_vals", "y2_meta", "colidx", "dy1_vals"))
+    rng = np.random.default_rng(1000 + M)
+
+    rows = np.sort(rng.choice(T, 32, replace=False))
+    assert_gemm_close(y1[rows], oracle.spmm24(inp["X"][rows], sv["w1_vals"], sv["w1_meta"], inp["b1"]), "y1 rows")
+    assert_gemm_close(dy2[rows], oracle.spmm24(inp["dY"][rows], sv["w2t_vals"], sv["w2t_meta"], None), "dy2 rows")
+
+    dense_y2, dense_dy1 = {}, {}
+    for tb in sorted(set(int(b) for b in rng.choice(T // 64, 6, replace=False)) | {0, T // 64 - 1}):
+        r = slice(64 * tb, 64 * tb + 64)
+        ov, om, oc = oracle.sqrelu_vnm_compress(y1[r], 64, M)
+        assert np.array_equal(yc[tb:tb + 1], oc) and np.array_equal(ym[r], om) and np.array_equal(yv[r], ov)
+        assert np.array_equal(dv[r], oracle.dsqrelu_vnm(dy2[r], y1[r], om, oc, 64, M))
+        dense_y2[tb] = oracle.vnm_decompress(ov, om, oc, 64, M)
+        dense_dy1[tb] = oracle.vnm_decompress(dv[r], om, oc, 64, M)
+        assert np.count_nonzero(dense_y2[tb]) <= 64 * F * 2 // M
+
+    # eqs. (3), (7): every row of the checked token blocks' first and last four rows
+    for tb in dense_y2:
+        sel = np.array([0, 1, 2, 3, 60, 61, 62, 63])
+        assert_gemm_close(Y3[64 * tb + sel], oracle.dense_nt(dense_y2[tb][sel], inp["W2"]), "y3 rows")
+        assert_gemm_close(dX[64 * tb + sel], oracle.dense_nt(dense_dy1[tb][sel], np.ascontiguousarray(inp["W1"].T)), "dX rows")
+
+    # eqs. (5), (8): two whole column blocks of M hidden units, contracted over all tokens
+    for blk in rng.choice(F // M, 2, replace=False):
+        cols = np.arange(blk * M, blk * M + M)
+        nib = np.empty((T, F // M), dtype=np.uint8)
+        nib[:, 0::2] = ym & 0xF
+        nib[:, 1::2] = ym >> 4
+        sub_m = (nib[:, blk:blk + 1] | (np.uint8(0x4) << 4)).astype(np.uint8)   # a second, empty block completes the metadata byte
+        for vals, G, got in ((yv, inp["dY"], np.ascontiguousarray(dW2[:, cols].T)), (dv, inp["X"], dW1[cols])):
+            sub_v = np.zeros((T, 4), dtype=np.uint16)
+            sub_v[:, :2] = vals.reshape(T, F // M, 2)[:, blk]
+            sub_c = np.zeros((T // 64, 2, 4), dtype=np.uint8)
+            sub_c[:, 0] = yc[:, blk]
+            sub_c[:, 1] = np.arange(4, dtype=np.uint8)
+            a = oracle.bits_to_f64(oracle.vnm_decompress(sub_v, sub_m, sub_c, 64, M))[:, :M]
+            assert_gemm_close(got, oracle.f64_to_bits(a.T @ oracle.bits_to_f64(G)), "wgrad columns")

@@ -365,10 +365,32 @@ def test_wide_block_consumers(M):
     assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.vnm_spmm(iv, im, ic, Wi, 0, 64, M)))
 
 
-@pytest.mark.parametrize("M,mode", [(16, sffn.MODE_HARD), (32, sffn.MODE_SOFT), (64, sffn.MODE_HARD)])
-def test_ffn_sparse_step_wide_blocks(M, mode):
-    """ffn_sparse_step with V:2:M blocks of 16 / 32 / 64 columns, teacher-forced against the oracle stage by stage."""
-    T, D, F = 320, 192, 640
+@pytest.mark.parametrize("M", [16, 32, 64])
+@pytest.mark.parametrize("T,F,N", [(192, 1024, 320), (64, 2048, 256), (128, 3072, 64)])
+def test_vnm_spmm_gathered_rows(M, T, F, N):
+    """eqs. (3), (7) for M >= 16 on the kernel that gathers the kept rows of the dense operand (4 F / M a multiple of
+    64): both orientations of the dense matrix against the oracle, and exactly on small integers."""
+    rng = np.random.default_rng(7 * M + T)
+    y1 = _y1_like(rng, T, F, 0.5)
+    av, am, ac = oracle.sqrelu_vnm_compress(y1, 64, M)
+    dav, dam, dac = to_dev(av), to_dev(am), to_dev(ac)
+    W2 = rnd_bits(rng, (N, F), 0.02)
+    W1 = rnd_bits(rng, (F, N), 0.02)
+    assert_gemm_close(to_bits(sffn.vnm_spmm(dav, dam, dac, to_dev(W2), 0, 64, M)), oracle.vnm_spmm(av, am, ac, W2, 0, 64, M), "y3")
+    assert_gemm_close(to_bits(sffn.vnm_spmm(dav, dam, dac, to_dev(W1), 1, 64, M)), oracle.vnm_spmm(av, am, ac, W1, 1, 64, M), "dX")
+    yi = bf16_bits_from_f32(rng.integers(-3, 4, size=(T, F)).astype(np.float32))
+    Wi = bf16_bits_from_f32(rng.integers(-2, 3, size=(F, N)).astype(np.float32))
+    iv, im, ic = oracle.sqrelu_vnm_compress(yi, 64, M)
+    got = to_bits(sffn.vnm_spmm(to_dev(iv), to_dev(im), to_dev(ic), to_dev(Wi), 1, 64, M))
+    assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.vnm_spmm(iv, im, ic, Wi, 1, 64, M)))
+
+
+@pytest.mark.parametrize("M,mode,F", [(16, sffn.MODE_HARD, 640), (32, sffn.MODE_SOFT, 640), (64, sffn.MODE_HARD, 640),
+                                      (16, sffn.MODE_SOFT, 1024), (32, sffn.MODE_HARD, 1024), (64, sffn.MODE_SOFT, 1024)])
+def test_ffn_sparse_step_wide_blocks(M, mode, F):
+    """ffn_sparse_step with V:2:M blocks of 16 / 32 / 64 columns, teacher-forced against the oracle stage by stage
+    (F = 640: eqs. (3), (7) on the plain-2:4 route; F = 1024: on the gathered-row kernel)."""
+    T, D = 320, 192
     inp = make_ffn_inputs(T, D, F, seed=7, zero_fraction=0.75)
     dev = {k: to_dev(v) for k, v in inp.items()}
     (Y3, dX, dW1, dW2), step = sffn.ffn_sparse_step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"], mode, M=M)
