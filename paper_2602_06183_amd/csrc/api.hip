@@ -176,8 +176,9 @@ int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_col
     uint8_t* m24 = ws + up256((size_t)T * Kfull);
     const uint16_t* W = Wd;
     uint16_t* wcopy = (uint16_t*)(m24 + up256((size_t)T * Kfull / 8));
-    if (vnm_spmm_gather_ok(T, N, Kfull, M) && Kfull * (w_kmajor ? ldw : N) * 2 < ((int64_t)1 << 32)) {
-        // M >= 16: contract over the 4 Kfull / M kept columns only, gathering their rows of the [Kfull, N] operand
+    if ((M >= 16 || w_kmajor) && vnm_spmm_gather_ok(T, N, Kfull, M) && Kfull * (w_kmajor ? ldw : N) * 2 < ((int64_t)1 << 32)) {
+        // contract over the 4 Kfull / M kept columns only, gathering their rows of the [Kfull, N] operand (M = 8: the two routes
+        // are equally fast, so it is taken only when it saves the transpose of Wd)
         int64_t ldk = ldw;
         if (!w_kmajor) {
             LAUNCH(launch_transpose(Wd, N, Kfull, ldw, wcopy, 0, nullptr, s), "vnm_spmm/transpose");

@@ -1,5 +1,5 @@
 // V:N:M activation x dense matrix with the dense operand's rows gathered per token block (eqs. (3), (7) of the paper
-// for blocks of M >= 16 columns, the regime of Table 5):
+// for blocks of M >= 16 columns, the regime of Table 5; also the stand-alone vnm_spmm at M = 8 when Wk is given as is):
 //     out[t, n] = sum_k' Ac[t, k'] * Wk[row(t / 64, k'), n],      row(tb, k') = (k' / 4) * M + colidx[tb, k' / 4, k' % 4]
 // Ac = the packed activation read as a plain 2:4 matrix of logical width K' = 4 F / M (vals [T, K' / 2], meta
 // [T, K' / 8], both row-major: exactly the canonical V:N:M arrays), Wk = [F, ldw] with the contraction index as row.
@@ -221,13 +221,13 @@ __global__ void __launch_bounds__(256) vnm_spmm_gather_kernel(const uint16_t* __
 
 bool vnm_spmm_gather_ok(int64_t T, int64_t N, int64_t F, int M) {
     const int64_t Kc = 4 * F / M;
-    return M >= 16 && T % 64 == 0 && N % 64 == 0 && Kc % 64 == 0 && Kc <= kGMaxKc;
+    return M >= 8 && T % 64 == 0 && N % 64 == 0 && Kc % 64 == 0 && Kc <= kGMaxKc;
 }
 
 hipError_t launch_vnm_spmm_gather(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* colidx, const uint16_t* Wk, int64_t ldw,
                                   int64_t T, int64_t N, int64_t F, int M, uint16_t* out, int64_t ldo, hipStream_t s) {
     if (!vnm_spmm_gather_ok(T, N, F, M) || ldw < N || F * ldw * 2 >= ((int64_t)1 << 32)) return hipErrorInvalidValue;
-    const int Kc = (int)(4 * F / M), logM = M == 16 ? 4 : M == 32 ? 5 : 6;
+    const int Kc = (int)(4 * F / M), logM = M == 8 ? 3 : M == 16 ? 4 : M == 32 ? 5 : 6;
     const int nblk_tok = (int)(T / 64), tiles_n = (int)((N + 255) / 256);
     hipLaunchKernelGGL(vnm_spmm_gather_kernel, dim3((unsigned)(nblk_tok * tiles_n)), dim3(256), 0, s, a_vals, a_meta, colidx, Wk, (int)ldw, (int)N,
                        Kc, logM, nblk_tok, tiles_n, out, ldo);

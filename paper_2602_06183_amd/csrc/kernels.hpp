@@ -61,7 +61,7 @@ hipError_t launch_vnm_to_24_m(const uint16_t* vals, const uint8_t* meta, const u
                               uint16_t* vals24, uint8_t* meta24, hipStream_t s);
 hipError_t launch_vnm_expand_t_m(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F, int M,
                                  uint16_t* out, hipStream_t s);
-// eqs. (3), (7) for M >= 16 with the rows of the dense operand gathered per token block (gemm_gather.hip):
+// eqs. (3), (7) with the rows of the dense operand gathered per token block (gemm_gather.hip):
 // out[t, n] = sum over the kept columns f of A[t, f] * Wk[f, n]; Wk = [F, ldw] (contraction index = row).
 // vnm_spmm_gather_ok: shapes the kernel covers (4 F / M a multiple of 64 and at most 7168); others take the plain-2:4 route.
 bool vnm_spmm_gather_ok(int64_t T, int64_t N, int64_t F, int M);

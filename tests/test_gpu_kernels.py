@@ -365,11 +365,12 @@ def test_wide_block_consumers(M):
     assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.vnm_spmm(iv, im, ic, Wi, 0, 64, M)))
 
 
-@pytest.mark.parametrize("M", [16, 32, 64])
+@pytest.mark.parametrize("M", [8, 16, 32, 64])
 @pytest.mark.parametrize("T,F,N", [(192, 1024, 320), (64, 2048, 256), (128, 3072, 64)])
 def test_vnm_spmm_gathered_rows(M, T, F, N):
-    """eqs. (3), (7) for M >= 16 on the kernel that gathers the kept rows of the dense operand (4 F / M a multiple of
-    64): both orientations of the dense matrix against the oracle, and exactly on small integers."""
+    """eqs. (3), (7) on the kernel that gathers the kept rows of the dense operand (4 F / M a multiple of 64; M = 8 takes
+    it only when the dense matrix is already row-gatherable, w_kmajor = 1): both orientations of the dense matrix
+    against the oracle, and exactly on small integers."""
     rng = np.random.default_rng(7 * M + T)
     y1 = _y1_like(rng, T, F, 0.5)
     av, am, ac = oracle.sqrelu_vnm_compress(y1, 64, M)
