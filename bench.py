@@ -176,7 +176,7 @@ def main():
                 "issued": round(exe / (avg_ms * 1e-3) / 1e12, 2), "issued_frac": round(exe / (avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
     # ---- the two compressors alone (HBM-bound; algorithmic bytes = input read once + packed outputs) -----------
-    def gbs(fn, nbytes, n=10):
+    def ms_of(fn, n=10):
         fn()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)   # the binding launches on torch's current stream
@@ -185,7 +185,10 @@ def main():
             fn()
         e1.record()
         e1.synchronize()
-        return round(nbytes / (e0.elapsed_time(e1) * 1e-3 / n) / 1e9, 1)
+        return e0.elapsed_time(e1) / n
+
+    def gbs(fn, nbytes, n=10):
+        return round(nbytes / (ms_of(fn, n) * 1e-3) / 1e9, 1)
 
     w1_one, w2_one = (W1[0], W2[0]) if moe else (W1, W2)
     y1_one = y1[:min(Tp, 16384)]
@@ -195,22 +198,25 @@ def main():
         "sqrelu_vnm_compress GB/s": gbs(lambda: sffn.sqrelu_vnm_compress(y1_one), (2 + 0.5 + 0.0625 + 1.0 / 128) * y1_one.shape[0] * F),
         "hbm_peak GB/s": HBM_PEAK_GBS,
     }
+    for m in (16, 32, 64):       # Table 5's block widths: bytes = input + packed values (2 of m) + metadata + column offsets
+        kernels["sqrelu_vnm_compress 64:2:%d GB/s" % m] = gbs(lambda: sffn.sqrelu_vnm_compress(y1_one, 64, m),
+                                                              (2 + 4.0 / m + 0.5 / m + 4.0 / (64 * m)) * y1_one.shape[0] * F)
+    # the paper's 2:4 micro-benchmark shape (Section 5.2.3): (m, n, k) = (4096, 16384, 4096), pruning included and excluded
+    gx = torch.randn((4096, 4096), device="cuda").to(torch.bfloat16)
+    gw = (torch.randn((16384, 4096), device="cuda") * 0.02).to(torch.bfloat16)
+    gout = torch.empty((4096, 16384), dtype=torch.bfloat16, device="cuda")
+    t_d = ms_of(lambda: torch.mm(gx, gw.t(), out=gout))
+    gv, gm = sffn.prune24_compress(gw, False, mode)
+    t_s = ms_of(lambda: sffn.spmm24_fwd(gx, gv, gm))
+    t_p = ms_of(lambda: sffn.prune24_compress(gw, False, mode))
+    gemm24 = {"shape_mnk": [4096, 16384, 4096], "dense_ms": round(t_d, 4), "spmm24_ms": round(t_s, 4), "prune24_ms": round(t_p, 4),
+              "speedup_vs_dense": round(t_d / t_s, 3), "speedup_with_pruning": round(t_d / (t_s + t_p), 3)}
+    del gx, gw, gout, gv, gm
 
     # ---- the activation GEMM alone for every block width of Table 5, against the dense GEMM of the same shape
     #      (Section 5.2.3's micro-benchmark): out[T, D] = y2v[T, F] @ W1[F, D], eq. (7)'s orientation ------------------
     venom = None
     if not moe:
-        def ms_of(fn, n=10):
-            fn()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(n):
-                fn()
-            e1.record()
-            e1.synchronize()
-            return e0.elapsed_time(e1) / n
-
         dense_out = torch.empty((y1_one.shape[0], D), dtype=torch.bfloat16, device="cuda")
         t_dense = ms_of(lambda: torch.mm(y1_one, w1_one, out=dense_out))
         venom = {"shape": "[%d, %d] x [%d, %d]" % (y1_one.shape[0], F, F, D), "dense_ms": round(t_dense, 4)}
@@ -272,6 +278,7 @@ def main():
         "stage_ms": {k: round(v, 4) for k, v in acc.items()},
         "standalone_kernels": kernels,
         "venom_gemm_microbench": venom,
+        "gemm24_microbench": gemm24,
         "retained_l1_fraction": retained, "relu_zero_fraction": zero_frac,
         "roofline": roofline, "cpu_baseline": cpu,
         "paper_context": "paper reports 1.4-1.5x for 2:4 GEMMs and 1.4-1.7x end-to-end on NVIDIA sparse tensor cores (Sections 1, 5.2.3); context, not a target",
