@@ -285,16 +285,20 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     uint16_t* ykept = (uint16_t*)(ws + L.pub.y1_kept);
     const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
     if (cfg->M != 8) {
-        // Wider blocks (Table 5): the same Alg. 1 / Alg. 2 from the stand-alone kernels on row-major operands; the
-        // V:2:M activation is still a valid plain 2:4 matrix over all F columns, so eqs. (3), (7) stay on smfmac.
-        // The dense y1 and dy2 are always stored (they are what eq. (6) reads), y1_kept is not produced.
+        // Wider blocks (Table 5): the same Alg. 1 / Alg. 2 without the fused epilogues.  Eqs. (1), (4) run on the blocked
+        // operands like the M = 8 step but only store the dense y1 / dy2 (they are what the stand-alone eq. (2) / eq. (6)
+        // kernels read; y1_kept is not produced); eqs. (3), (7) gather the kept rows of W2.T / W1; eqs. (5), (8) contract
+        // the expanded transposed activation.
         const int M = cfg->M;
         if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
         uint16_t* at = atb;                              // dense [F, T]
-        uint16_t* tr = xtb;                              // transposes: dY.T, W1.T, X.T in turn ([D, T] or [D, F])
-        uint16_t* w1t = w1tb;
-        STAGE(launch_prune24(W1, F, D, D, 0, cfg->mode, w1v, w1m, s), "step/prune24(W1)");
-        STAGE(launch_gemm_nt(1, w1v, w1m, X, b1, F, T, D, 1, y1, F, s), "step/y1");                                   // eq. (1)
+        uint16_t* xt = xtb;                              // X.T and dY.T [D, T], row-major here
+        uint16_t* dyt = dytb;
+        uint16_t* w1t = w1tb;                            // W2.T (gathered route) or W1.T (plain-2:4 route), [F, D] / [D, F] row-major
+        const VnmEpilogue plain;                         // eqs. (1), (4) on the blocked operands, dense output only
+        STAGE(launch_transpose(X, T, D, D, xt, 0, xb, s), "step/X.T");
+        STAGE(launch_prune24_step(W1, F, D, D, 0, cfg->mode, w1v, w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
+        STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, plain, s), "step/y1");                        // eq. (1)
         STAGE(launch_sqrelu_vnm_compress_m(y1, T, F, M, y2v, y2m, cix, s), "step/sqrelu_vnm_compress");               // eq. (2), Section 2.3
         // eqs. (3), (7): gather the kept rows of the dense operand (matrix work and traffic shrink with 4 / M); shapes the
         // gathered kernel does not cover re-express the activation as plain 2:4 over all F columns instead
@@ -306,11 +310,12 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
             STAGE(launch_vnm_to_24_m(y2v, y2m, cix, T, F, M, a24v, a24m, s), "step/to24(y2)");
             STAGE(launch_gemm_nt(1, a24v, a24m, W2, nullptr, T, D, F, 0, Y3, D, s), "step/y3");                       // eq. (3)
         }
-        STAGE(launch_prune24(W2, F, D, F, 1, cfg->mode, w2v, w2m, s), "step/prune24(W2.T)");
-        STAGE(launch_gemm_nt(1, w2v, w2m, dY, nullptr, F, T, D, 1, dy2, F, s), "step/dy2");                           // eq. (4)
+        STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, w2v, w2m, w2vb, w2mb, nullptr, s), "step/prune24(W2.T)");
+        // eq. (5) before eq. (4): the weight-gradient kernel is faster while dY.T is still in the last-level cache
+        STAGE(launch_transpose(dY, T, D, D, dyt, 0, dyb, s), "step/dY.T");
         STAGE(launch_vnm_expand_t_m(y2v, y2m, cix, T, F, M, at, s), "step/expand(y2)");
-        STAGE(launch_transpose(dY, T, D, D, tr, 0, nullptr, s), "step/dY.T");
-        STAGE(launch_gemm_nt(0, at, nullptr, tr, nullptr, F, D, T, 1, dW2, F, s), "step/dW2");                        // eq. (5)
+        STAGE(launch_gemm_nt(0, at, nullptr, dyt, nullptr, F, D, T, 1, dW2, F, s), "step/dW2");                       // eq. (5)
+        STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, plain, s), "step/dy2");                // eq. (4)
         STAGE(launch_dsqrelu_vnm_m(dy2, y1, y2m, cix, T, F, M, dy1v, s), "step/dsqrelu_vnm");                         // eq. (6)
         if (gather) {
             STAGE(launch_vnm_spmm_gather(dy1v, y2m, cix, W1, D, T, D, F, M, dX, D, s), "step/dX");                    // eq. (7)
@@ -320,8 +325,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
             STAGE(launch_gemm_nt(1, a24v, a24m, w1t, nullptr, T, D, F, 0, dX, D, s), "step/dX");                      // eq. (7)
         }
         STAGE(launch_vnm_expand_t_m(dy1v, y2m, cix, T, F, M, at, s), "step/expand(dy1)");
-        STAGE(launch_transpose(X, T, D, D, tr, 0, nullptr, s), "step/X.T");
-        STAGE(launch_gemm_nt(0, at, nullptr, tr, nullptr, F, D, T, 0, dW1, D, s), "step/dW1");                        // eq. (8)
+        STAGE(launch_gemm_nt(0, at, nullptr, xt, nullptr, F, D, T, 0, dW1, D, s), "step/dW1");                        // eq. (8)
         (void)keep_dense;
         return SFFN_OK;
     }

@@ -500,7 +500,10 @@ hipError_t launch_gemm_vnm_epilogue(const uint16_t* a_vals, const uint8_t* a_met
     const unsigned tiles = grid_tiles(tiles_m, tiles_n, g);
     if (tiles == 0) return hipSuccess;
     dim3 grid(tiles);
-    if (ep.mode == 1)
+    if (ep.mode == 0)       // no V:N:M work: the dense output only
+        hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 0, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
+                           tiles_m, tiles_n, ep, g);
+    else if (ep.mode == 1)
         hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 1, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
                            tiles_m, tiles_n, ep, g);
     else

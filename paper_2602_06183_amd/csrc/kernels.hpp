@@ -14,7 +14,7 @@ namespace sffn {
 //          vals (= dy1 values), v24 / m24 and at as above.
 //   store_dense: also write the dense GEMM output (y1 / dy2) to `out`.
 struct VnmEpilogue {
-    int mode = 0;
+    int mode = 0;                   // 0: no V:N:M epilogue, only the dense output
     int store_dense = 1;
     uint16_t* vals = nullptr;
     uint8_t* meta = nullptr;
