@@ -114,7 +114,12 @@ int spmm24_dgrad(const uint16_t* dY, const uint16_t* wt_vals, const uint8_t* wt_
 /* eq. (3) / Alg. 1 line 7 (w_kmajor=0, Wd = W2 [N,Kfull]) and eq. (7) / Alg. 2 line 5
  * (w_kmajor=1, Wd = W1 [Kfull,N]): out[t,n] = bf16( sum_f Av[t,f] * W(n,f) ) with Av the V:N:M
  * matrix (a_vals [T,Kfull/4], a_meta [T,Kfull/16], a_colidx [T/64,Kfull/8,4]) and W dense.
- * ldw = row stride of Wd in elements.  workspace: sffn_vnm_spmm_workspace_bytes(). */
+ * ldw = row stride of Wd in elements.  workspace: sffn_vnm_spmm_workspace_bytes() (the same size
+ * for both orientations: scratch for the activation re-expressed as plain 2:4 and for a transposed
+ * copy of Wd).  Route: when 4*Kfull/M is a multiple of 64 and at most 7168 (and M >= 16, or M = 8
+ * with w_kmajor=1) only the kept rows of the contraction-major W take part (gathered per 64-token
+ * block); otherwise the activation is contracted as a plain 2:4 matrix over all Kfull columns.
+ * Both routes compute the same sums (fp32 accumulation order differs). */
 int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_colidx,
              const uint16_t* Wd, int64_t ldw, int w_kmajor, int64_t T, int64_t N, int64_t Kfull,
              int V, int M, uint16_t* out, void* workspace, size_t ws_bytes, void* stream);
@@ -134,9 +139,9 @@ int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_co
 /* Alg. 1 + Alg. 2, one call: X [T,D], W1 [F,D], W2 [D,F], b1 fp32 [F] or NULL, dY [T,D] ->
  * Y3 [T,D], dX [T,D], dW1 [F,D], dW2 [D,F]; intermediates land in `workspace` at the offsets of
  * sffn_workspace_layout().  Both weight matrices are re-pruned inside the call.
- * cfg->M = 16, 32 or 64: the same algorithm from the stand-alone kernels (the V:2:M activation is still a plain 2:4
- * matrix over all F columns, so eqs. (3), (7) stay on the structured-sparse matrix cores); the dense y1 and dy2 are
- * then always stored, y1_kept is not produced, and the packed activation tensors have the sizes given above. */
+ * cfg->M = 16, 32 or 64 (Table 5): the same algorithm without the fused epilogues: eqs. (2), (6) run as separate
+ * kernels, eqs. (3), (7) contract only the kept rows of W2.T / W1 (see vnm_spmm; same fallback rule); the dense y1 and
+ * dy2 are then always stored, y1_kept is not produced, and the packed activation tensors have the sizes given above. */
 int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, const uint16_t* W2,
                     const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
                     uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
