@@ -338,6 +338,9 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     const GemmGroup* gd = g.n ? &g_dense : nullptr;
     const GemmGroup* gw = g.n ? &g_wgrad : nullptr;
 
+    // eq. (7) on the gathered-row kernel when it covers the shape: W1 is already contraction-major, so its transpose and
+    // the plain-2:4 view of dy1 are not needed (measured 0.015 ms per step faster at the 1B shape)
+    const bool gather_dx = g.n == 0 && vnm_spmm_gather_ok(T, D, F, 8) && F * D * 2 < ((int64_t)1 << 32);
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
     // Every GEMM operand is first brought into the blocked layout by the kernel that reads or produces it
     // anyway: X, dY and W1 by the transposes the weight-gradient / input-gradient GEMMs need, W2 by its
@@ -360,11 +363,15 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     {   // eq. (4), then eq. (6) on y2's kept slots; overwrites the 2:4 view and the transposed tile with dy1's
         VnmEpilogue ep;
         ep.mode = 2; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
-        ep.v24 = a24v; ep.m24 = a24m; ep.at = atb;
+        ep.v24 = gather_dx ? nullptr : a24v; ep.m24 = a24m; ep.at = atb;
         STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, ep, s, gp), "step/dy2+dsqrelu_vnm");
     }
-    STAGE(launch_transpose(W1, F, D, D, w1tb, 1, nullptr, s, (int)E), "step/W1.T");
-    STAGE(launch_spmm_blocked(a24v, a24m, w1tb, nullptr, T, D, F, 0, dX, D, s, gd), "step/dX");           // eq. (7)
+    if (gather_dx) {
+        STAGE(launch_vnm_spmm_gather(dy1v, y2m, cix, W1, D, T, D, F, 8, dX, D, s), "step/dX");                // eq. (7)
+    } else {
+        STAGE(launch_transpose(W1, F, D, D, w1tb, 1, nullptr, s, (int)E), "step/W1.T");
+        STAGE(launch_spmm_blocked(a24v, a24m, w1tb, nullptr, T, D, F, 0, dX, D, s, gd), "step/dX");       // eq. (7)
+    }
     STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                           // eq. (8)
     return SFFN_OK;
 }

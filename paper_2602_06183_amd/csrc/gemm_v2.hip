@@ -404,11 +404,13 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             vals_p[(int64_t)it * 8 * (F / 8)] = v;
                         }
                         // the same block as two plain 2:4 groups (blocked operand of eq. (3) / eq. (7))
-                        uint32_t a24, b24, mb8;
-                        vnm_block_to_24(v, nib, cw, a24, b24, mb8);
-                        const uint32_t m2 = mb8 | (row_shl<1>(mb8) << 8);     // two column blocks = 16 k = one lane's half-word of a unit
-                        *reinterpret_cast<uint2*>(v24_p + (int64_t)(it >> 1) * (F / 64) * 512 + (it & 1) * 256) = make_uint2(a24, b24);
-                        if ((lane & 1) == 0) *reinterpret_cast<uint16_t*>(m24_p + (int64_t)(it >> 2) * (F / 64) * 256 + (it & 3) * 32) = (uint16_t)m2;
+                        if (ep.v24) {       // (not wanted when eq. (7) gathers rows from the canonical arrays)
+                            uint32_t a24, b24, mb8;
+                            vnm_block_to_24(v, nib, cw, a24, b24, mb8);
+                            const uint32_t m2 = mb8 | (row_shl<1>(mb8) << 8);     // two column blocks = 16 k = one lane's half-word of a unit
+                            *reinterpret_cast<uint2*>(v24_p + (int64_t)(it >> 1) * (F / 64) * 512 + (it & 1) * 256) = make_uint2(a24, b24);
+                            if ((lane & 1) == 0) *reinterpret_cast<uint16_t*>(m24_p + (int64_t)(it >> 2) * (F / 64) * 256 + (it & 3) * 32) = (uint16_t)m2;
+                        }
                         // transposed tile for the weight-gradient GEMM, compacted to the block's four kept hidden units:
                         // row = 4 * block + position among the kept units, column = token
                         *reinterpret_cast<uint16_t*>(ttile + (bl * 4 + (nib & 3u)) * EP + t * 2) = (uint16_t)(v & 0xFFFFu);
