@@ -100,8 +100,11 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     //      are clamped into it: they only feed outputs that are never stored. --------------------------
     constexpr int A_LD = C::A_BYTES / 1024 / 8;          // dma16 issues per wave for A
     constexpr int B_LD = C::B_BYTES / 1024 / 8;
+    // Row-major operands of the sparse kernel: a B row's 64 k of a stage are one 128-byte line, fetched whole (8 rows per
+    // load, tile [256][128 bytes], 16-byte chunks swizzled by (row / 2) % 8) rather than as two 64-byte halves.
+    constexpr bool lineB = SPARSE && !BLOCKED;
     uint64_t a_base[A_LD], b_base[B_LD], m_base = 0;     // wave-uniform byte addresses of kt = 0
-    uint32_t a_lane, b_lane, m_lane;                     // per-lane byte offsets
+    uint32_t a_lane, b_lane, b_lane1 = 0, m_lane;        // per-lane byte offsets (b_lane1: odd loads of the line layout)
     uint32_t a_kstep, b_kstep, m_kstep;                  // bytes per main-loop step
     {
         const int rb = lane >> 2;                                        // row inside the 16-row group
@@ -117,10 +120,16 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
             // SPARSE: a stage holds 64 k of B as two half-tiles (k 0-31, k 32-63), each laid out like the A tile
             const int bk = wave * B_LD + n, h = SPARSE ? (bk >> 4) : 0;
             int gr = j0 + (bk & 15) * 16; gr = gr < Rb ? gr : Rb - 16;
-            b_base[n] = uniform64(blocked ? B + (((int64_t)(gr >> 4) * KCb + h) << 9) : B + (int64_t)gr * Kld + h * 32);
+            if (lineB) { gr = j0 + bk * 8; gr = gr < Rb ? gr : Rb - 8; }
+            b_base[n] = uniform64(blocked ? B + (((int64_t)(gr >> 4) * KCb + h) << 9) : lineB ? B + (int64_t)gr * Kld : B + (int64_t)gr * Kld + h * 32);
         }
         a_lane = blocked ? (rb * 32 + c * 8) * 2 : (uint32_t)(rb * lda + c * 8) * 2;
         b_lane = blocked ? (rb * 32 + c * 8) * 2 : (uint32_t)(rb * Kld + c * 8) * 2;
+        if (lineB) {        // lane -> (row lane / 8 of the load's 8 rows, slot lane % 8); tile row = 8 * load + row, load parity = n % 2
+            const int r8 = lane >> 3, slot = lane & 7;
+            b_lane = (uint32_t)(r8 * Kld + ((slot ^ (r8 >> 1)) * 8)) * 2;
+            b_lane1 = (uint32_t)(r8 * Kld + ((slot ^ (4 + (r8 >> 1))) * 8)) * 2;
+        }
         // metadata: one 4-byte-per-lane load brings 32 rows x 64 k; blocked: one unit of common.hpp, lane-linear;
         // row-major: lane -> (row lane / 2, 4-byte half lane % 2), landing as [row][8 bytes]
         m_lane = blocked ? lane * 4 : (uint32_t)((lane >> 1) * (Kld / 8) + (lane & 1) * 4);
@@ -139,15 +148,15 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         unsigned char* sm = sb + C::B_BYTES;
         // the k position goes into the 32-bit per-lane offset (one vector add per operand); the bases stay put in SGPRs
         if (h == 0) {
-            const uint32_t ao = a_lane + (uint32_t)kt * a_kstep, bo = b_lane + (uint32_t)kt * b_kstep;
+            const uint32_t ao = a_lane + (uint32_t)kt * a_kstep, bo = b_lane + (uint32_t)kt * b_kstep, bo1 = b_lane1 + (uint32_t)kt * b_kstep;
 #pragma unroll
             for (int n = 0; n < A_LD; ++n) dma16(a_base[n], ao, sa + (wave * A_LD + n) * 1024);
 #pragma unroll
-            for (int n = 0; n < B_LD / 2; ++n) dma16(b_base[n], bo, sb + (wave * B_LD + n) * 1024);
+            for (int n = 0; n < B_LD / 2; ++n) dma16(b_base[n], (lineB && (n & 1)) ? bo1 : bo, sb + (wave * B_LD + n) * 1024);
         } else {
-            const uint32_t bo = b_lane + (uint32_t)kt * b_kstep;
+            const uint32_t bo = b_lane + (uint32_t)kt * b_kstep, bo1 = b_lane1 + (uint32_t)kt * b_kstep;
 #pragma unroll
-            for (int n = B_LD / 2; n < B_LD; ++n) dma16(b_base[n], bo, sb + (wave * B_LD + n) * 1024);
+            for (int n = B_LD / 2; n < B_LD; ++n) dma16(b_base[n], (lineB && (n & 1)) ? bo1 : bo, sb + (wave * B_LD + n) * 1024);
             if (SPARSE) dma4(m_base, m_lane + (uint32_t)kt * m_kstep, sm + wave * 256);
         }
     };
@@ -166,6 +175,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     for (int b = 0; b < FN; ++b) {
         const int row = wn * WN + b * 32 + l32;
         b_off[b] = C::A_BYTES + row * 64 + ((lh ^ ((row >> 2) & 3)) << 4);      // SPARSE: + 16 KB for the second k half
+        if (lineB) b_off[b] = C::A_BYTES + row * 128 + ((lh ^ ((row >> 1) & 7)) << 4);   // chunk = 4 ks + 2 u + lh
     }
 
     f32x16 acc[FM][FN];
@@ -194,7 +204,10 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         }
     };
     auto read_b = [&](FragSet& f, const unsigned char* st, int ks, int b) {
-        if (SPARSE) {
+        if (lineB) {
+            f.b16[b].u[0] = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ (64 * ks)));
+            f.b16[b].u[1] = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ (64 * ks + 32)));
+        } else if (SPARSE) {
             f.b16[b].u[0] = *reinterpret_cast<const uint4*>(st + b_off[b] + 16384 * ks);
             f.b16[b].u[1] = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ 32) + 16384 * ks);
         } else {
