@@ -1,0 +1,141 @@
+"""Pins for the oracle's neuron-level router (paper Section 3.3, Alg. 3, the three conversion steps of Section 3.4)."""
+import numpy as np
+import pytest
+
+import oracle
+from workload import make_router_inputs
+
+
+def bf(x):
+    return oracle.f32_to_bits(np.asarray(x, dtype=np.float32))
+
+
+def test_route_scores_exact_on_small_integers_and_close_to_float64():
+    rng = np.random.default_rng(0)
+    x = rng.integers(-4, 5, size=(37, 192)).astype(np.float32)
+    m = rng.integers(-3, 4, size=(5, 192)).astype(np.float32)
+    s = oracle.route_scores(bf(x), bf(m))
+    assert s.dtype == np.float32 and np.array_equal(s, (x.astype(np.float64) @ m.astype(np.float64).T).astype(np.float32))
+    xr, mr = bf(rng.standard_normal((64, 512))), bf(rng.standard_normal((4, 512)))
+    ref = oracle.bits_to_f64(xr) @ oracle.bits_to_f64(mr).T
+    mag = np.abs(oracle.bits_to_f64(xr)) @ np.abs(oracle.bits_to_f64(mr)).T
+    # 8 sequential + 6 tree additions, each within half an ulp of a partial sum bounded by the sum of magnitudes
+    assert np.all(np.abs(oracle.route_scores(xr, mr) - ref) <= 14 * 2.0 ** -24 * mag)
+
+
+def test_route_scores_summation_order():
+    """A vector on which the stated order (lane-strided partial sums, then folding by 32, 16, ...) and the plain
+    left-to-right order give different float32 results: products 2^24 at d = 0, -2^24 at d = 32, 1 at d = 64.
+    Stated order: lane 0 holds 2^24 + 1 -> 2^24 (tie to even), lane 32 holds -2^24, the fold gives 0.
+    Left to right (or exact arithmetic) gives 1."""
+    x = np.zeros((1, 128), dtype=np.float32)
+    m = np.zeros((1, 128), dtype=np.float32)
+    x[0, 0], m[0, 0] = 4096.0, 4096.0
+    x[0, 32], m[0, 32] = -4096.0, 4096.0
+    x[0, 64], m[0, 64] = 1.0, 1.0
+    assert (x.astype(np.float64) @ m.astype(np.float64).T)[0, 0] == 1.0
+    assert oracle.route_scores(bf(x), bf(m))[0, 0] == 0.0
+    # moving the 1 to another lane keeps it: lane 1 = 1, the fold adds it last enough to survive
+    x[0, 64], m[0, 64] = 0.0, 0.0
+    x[0, 65], m[0, 65] = 1.0, 1.0
+    assert oracle.route_scores(bf(x), bf(m))[0, 0] == 1.0
+
+
+def test_route_top1_brute_force_ties_and_cosine():
+    s = np.array([[1.0, 3.0, 3.0, -1.0], [2.0, 2.0, 2.0, 2.0], [-5.0, -4.0, -4.5, -4.0], [0.0, -0.0, 0.0, 0.0]], dtype=np.float32)
+    assert list(oracle.route_top1(s)) == [1, 0, 1, 0]
+    rng = np.random.default_rng(1)
+    s = rng.integers(-3, 4, size=(500, 6)).astype(np.float32)
+    want = [min(e for e in range(6) if row[e] == max(row)) for row in s]
+    assert list(oracle.route_top1(s)) == want
+    # unit-length means: the dot product ranks experts as the cosine similarity does (Section 3.3 names both)
+    inp = make_router_inputs(256, 128, 256, 32, seed=5)
+    x, m = oracle.bits_to_f64(inp["X"]), oracle.bits_to_f64(inp["means"])
+    assert np.allclose(np.linalg.norm(m, axis=1), 1.0, atol=4e-3)           # bf16 storage of a unit vector
+    cos = (x @ m.T) / (np.linalg.norm(x, axis=1)[:, None] * np.linalg.norm(m, axis=1)[None, :])
+    got = oracle.route_top1(oracle.route_scores(inp["X"], inp["means"]))
+    top2 = np.sort(cos, axis=1)[:, -2:]
+    clear = (top2[:, 1] - top2[:, 0]) > 1e-2                                # margins far above bf16 norm error and fp32 rounding
+    assert clear.sum() > 128 and np.array_equal(got[clear], np.argmax(cos, axis=1)[clear])
+
+
+@pytest.mark.parametrize("T,E", [(0, 2), (1, 2), (200, 4), (777, 16), (640, 8)])
+def test_expert_permutation_properties(T, E):
+    rng = np.random.default_rng(T + E)
+    expert = rng.integers(0, E, size=T)
+    if T == 640:
+        expert[:] = 3                                                       # one expert takes everything
+    perm, seg = oracle.expert_permutation(expert, E)
+    assert len(perm) == (T + 63) // 64 * 64 + 64 * E and seg[0] == 0 and np.all(seg % 64 == 0)
+    real = perm[perm >= 0]
+    assert sorted(real) == list(range(T))                                   # every token exactly once
+    for e in range(E):
+        run = perm[seg[e]:seg[e + 1]]
+        tok = run[run >= 0]
+        n = int((expert == e).sum())
+        assert len(tok) == n and np.all(expert[tok] == e) and np.all(np.diff(tok) > 0)      # stable
+        assert np.all(run[:n] >= 0) and np.all(run[n:] < 0) and seg[e + 1] - seg[e] == (n + 63) // 64 * 64
+    assert np.all(perm[seg[E]:] < 0)
+
+
+def _literal_alg3(inp, M, expert, mode):
+    """Alg. 3 as printed: out = zeros; for every token, out[i] += x[i] @ W[expert] with W[expert] = the (2:4-pruned)
+    W1 restricted to the expert's hidden units; then eq. (2).  Dense [T, F] result, python loop over tokens."""
+    X, W1, b1 = oracle.bits_to_f64(inp["X"]), oracle.bits_to_f64(oracle.prune24_dense(inp["W1"], mode)), inp["b1"].astype(np.float64)
+    T, F = X.shape[0], W1.shape[0]
+    owner = (np.arange(F) % M) // 4
+    y2 = np.zeros((T, F), dtype=np.uint16)
+    for i in range(T):
+        We = np.where((owner == expert[i])[:, None], W1, 0.0)
+        out = X[i] @ We.T + np.where(owner == expert[i], b1, 0.0)
+        y2[i] = oracle.sqrelu(oracle.f64_to_bits(out[None, :]))[0]
+    return y2
+
+
+@pytest.mark.parametrize("M,mode", [(8, oracle.sparse24.HARD), (16, oracle.sparse24.SOFT), (32, oracle.sparse24.HARD)])
+def test_moe_to_venom_equals_literal_algorithm_then_24(M, mode):
+    T, D, F = 150, 64, 128
+    inp = make_router_inputs(T, D, F, M, seed=11, zero_fraction=0.5)
+    r = oracle.moe_to_venom(inp["X"], inp["W1"], inp["b1"], inp["means"], M, mode)
+    y2 = _literal_alg3(inp, M, r["expert"], mode)
+    dense = oracle.vnm_decompress(r["vals"], r["meta"], r["colidx"], 64, M)            # [Tcap, F]
+    real = r["perm"] >= 0
+    assert not dense[~real].any()
+    # brute-force 2:4 inside the expert's four columns of every block: keep the two largest, ties to the lower column
+    want = np.zeros_like(y2)
+    for i in range(T):
+        cols0 = 4 * r["expert"][i]
+        for g in range(F // M):
+            c = g * M + cols0 + np.arange(4)
+            v = y2[i, c]
+            order = sorted(range(4), key=lambda k: (-int(v[k] & 0x7FFF), k))[:2]
+            want[i, c[order]] = v[order]
+    assert np.array_equal(dense[real], want[r["perm"][real]])
+    assert (dense != 0).mean() <= 2.0 / M                                           # Table 5: sparsity at least 1 - N / M
+
+
+def test_router_output_is_what_section_2_3_would_select():
+    """The matrix Alg. 3 produces, written out densely in permuted row order, is V:N:M by construction: the magnitude
+    rule of Section 2.3 applied to it picks the expert's columns back (wherever each of them carries mass) and the same
+    packed values."""
+    M = 16
+    inp = make_router_inputs(1024, 64, 256, M, seed=2, zero_fraction=0.5)
+    r = oracle.moe_to_venom(inp["X"], inp["W1"], inp["b1"], inp["means"], M)
+    dense = oracle.vnm_decompress(r["vals"], r["meta"], r["colidx"], 64, M)
+    # the dense y2 before the per-row 2:4: scatter the compact y2 to its hidden units
+    y2c = oracle.sqrelu(r["y1c"])
+    y2c[r["perm"] < 0] = 0
+    full = np.zeros_like(dense)
+    for e in range(M // 4):
+        rows = slice(int(r["seg"][e]), int(r["seg"][e + 1]))
+        full[rows][:, oracle.cluster_rows(e, M, 256)] = y2c[rows]
+    vals, meta, colidx = oracle.vnm_compress(full, 64, M)
+    mass = oracle.bits_to_f64(full).reshape(-1, 64, 256 // M, M).sum(axis=1)            # [blocks, F / M, M]
+    ok = (np.take_along_axis(mass, r["colidx"].astype(np.int64), axis=-1) > 0).all(axis=-1)   # all four expert columns carry mass
+    assert ok.mean() > 0.5
+    assert np.array_equal(colidx[ok], r["colidx"][ok])
+    okr = np.repeat(ok, 64, axis=0)                                                      # [Tcap, F / M]
+    assert np.array_equal(vals.reshape(-1, 256 // M, 2)[okr], r["vals"].reshape(-1, 256 // M, 2)[okr])
+    # and the activation GEMM on it is the dense product with the masked matrix
+    y3 = oracle.vnm_spmm(r["vals"], r["meta"], r["colidx"], inp["W2"], 0, 64, M)
+    assert np.array_equal(y3, oracle.dense_nt(dense, inp["W2"]))

@@ -77,3 +77,23 @@ def make_moe_inputs(n_tokens, n_experts, top_k, D, F, seed=0, zero_fraction=0.90
         dY[a:a + int(counts[e])] = part["dY"]
         W1[e], W2[e], b1[e] = part["W1"], part["W2"], part["b1"]
     return dict(X=X, W1=W1, W2=W2, b1=b1, dY=dY, counts=counts, seg=seg)
+
+
+def make_router_inputs(T, D, F, M, seed=0, zero_fraction=0.90, w_std=0.02):
+    """Workload of the neuron-level router (Section 3.3): make_ffn_inputs plus the E = M / 4 expert means.
+    Expert e owns the hidden units f with (f mod M) / 4 == e (the offline clustering, taken as already applied to
+    the row order of W1); its mean is the average of those rows of W1 plus a random direction of comparable
+    size (random weights have no cluster structure of their own), normalised to unit length and stored as bf16.
+    Tokens then split unevenly but not degenerately over the experts."""
+    inp = make_ffn_inputs(T, D, F, seed, zero_fraction, w_std)
+    rng = np.random.default_rng(seed + 1000)
+    E = M // 4
+    w = _bits_to_f64(inp["W1"])
+    f = np.arange(F)
+    means = np.empty((E, D), dtype=np.float64)
+    for e in range(E):
+        m = w[(f % M) // 4 == e].mean(axis=0)
+        m = m + rng.standard_normal(D) * np.linalg.norm(m) / np.sqrt(D) * (1.0 + 0.5 * e / max(E - 1, 1))
+        means[e] = m / np.linalg.norm(m)
+    inp["means"] = bf16_bits_from_f32(means.astype(np.float32))
+    return inp
