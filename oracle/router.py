@@ -13,10 +13,10 @@ Readings fixed here because the paper is silent, garbled or at odds with itself:
   * Similarity.  The text says cosine distance in one place and the product x @ ExpertMeans in another.  The means
     are taken unit-normalised (an offline step), which makes the dot product rank experts exactly as the cosine
     does; expert(t) = argmax_e s[t, e], ties to the lower e.
-  * Arithmetic of s (it decides an integer, so it is part of the contract): float32; s[t, e] is the sum over 64
-    partial sums p_l, l = 0..63, p_l accumulating x[t, d] * mean[e, d] for d = l, l + 64, l + 128, ... in ascending d
-    (bf16 products are exact in float32, one rounding per add, start +0); the 64 partials are then folded
-    p_l + p_(l + 32) for l < 32, then + 16, 8, 4, 2, 1.
+  * Arithmetic of s (it decides an integer, so it is part of the contract): float32; the D products x[t, d] *
+    mean[e, d] (exact in float32 for bf16 factors) are cut into chunks of 8 consecutive d; partial sum p_l,
+    l = 0..63, accumulates the chunks l, l + 64, l + 128, ... in ascending d (start +0, one rounding per add); the
+    64 partials are then folded p_l + p_(l + 32) for l < 32, then + 16, 8, 4, 2, 1.
   * Permutation.  Stable: inside an expert's run tokens keep ascending order; every run is padded to a multiple of
     V = 64 rows; perm[r] is the token of row r or -1 for a padding row; the row capacity is ceil64(T) + 64 E, rows
     past the last run are padding too.
@@ -32,16 +32,21 @@ from .vnm import sqrelu
 
 
 def route_scores(x_bits, means_bits):
-    """s[t, e] in float32, accumulated in the order stated in the module header.  D must be a multiple of 64."""
+    """s[t, e] in float32, accumulated in the order stated in the module header.  D must be a multiple of 8."""
     x = bits_to_f32(np.asarray(x_bits, dtype=np.uint16))
     m = bits_to_f32(np.asarray(means_bits, dtype=np.uint16))
     T, D = x.shape
     E = m.shape[0]
-    assert D % 64 == 0 and m.shape[1] == D
+    assert D % 8 == 0 and m.shape[1] == D
     p = np.zeros((T, E, 64), dtype=np.float32)
-    for i in range(D // 64):
-        prod = (x[:, None, 64 * i:64 * i + 64] * m[None, :, 64 * i:64 * i + 64]).astype(np.float32)   # exact
-        p = (p + prod).astype(np.float32)
+    lane_d = 8 * np.arange(64)
+    for base in range(0, D, 512):                        # chunks base / 8 + l, l = 0..63, of this round
+        for k in range(8):
+            d = base + lane_d + k
+            live = d < D                                 # a lane whose chunk does not exist adds nothing
+            prod = np.zeros((T, E, 64), dtype=np.float32)
+            prod[:, :, live] = x[:, None, d[live]] * m[None, :, d[live]]           # exact in float32
+            p = np.where(live[None, None, :], (p + prod).astype(np.float32), p)
     w = 32
     while w >= 1:
         p = (p[..., :w] + p[..., w:2 * w]).astype(np.float32)

@@ -24,21 +24,29 @@ def test_route_scores_exact_on_small_integers_and_close_to_float64():
 
 
 def test_route_scores_summation_order():
-    """A vector on which the stated order (lane-strided partial sums, then folding by 32, 16, ...) and the plain
-    left-to-right order give different float32 results: products 2^24 at d = 0, -2^24 at d = 32, 1 at d = 64.
-    Stated order: lane 0 holds 2^24 + 1 -> 2^24 (tie to even), lane 32 holds -2^24, the fold gives 0.
-    Left to right (or exact arithmetic) gives 1."""
-    x = np.zeros((1, 128), dtype=np.float32)
-    m = np.zeros((1, 128), dtype=np.float32)
+    """A vector on which the stated order (64 partial sums over 8-element chunks taken round-robin, then folding by 32,
+    16, ...) and the plain left-to-right order give different float32 results: products 2^24 at d = 0 (chunk 0, lane
+    0), -2^24 at d = 256 (chunk 32, lane 32), 1 at d = 512 (chunk 64, lane 0 again).  Stated order: lane 0 holds
+    2^24 + 1 -> 2^24 (tie to even), lane 32 holds -2^24, the fold gives 0.  Left to right (or exact) gives 1."""
+    x = np.zeros((1, 1024), dtype=np.float32)
+    m = np.zeros((1, 1024), dtype=np.float32)
     x[0, 0], m[0, 0] = 4096.0, 4096.0
-    x[0, 32], m[0, 32] = -4096.0, 4096.0
-    x[0, 64], m[0, 64] = 1.0, 1.0
+    x[0, 256], m[0, 256] = -4096.0, 4096.0
+    x[0, 512], m[0, 512] = 1.0, 1.0
     assert (x.astype(np.float64) @ m.astype(np.float64).T)[0, 0] == 1.0
     assert oracle.route_scores(bf(x), bf(m))[0, 0] == 0.0
-    # moving the 1 to another lane keeps it: lane 1 = 1, the fold adds it last enough to survive
-    x[0, 64], m[0, 64] = 0.0, 0.0
-    x[0, 65], m[0, 65] = 1.0, 1.0
+    # the same 1 in the next chunk belongs to lane 1 and survives the folds
+    x[0, 512], m[0, 512] = 0.0, 0.0
+    x[0, 520], m[0, 520] = 1.0, 1.0
     assert oracle.route_scores(bf(x), bf(m))[0, 0] == 1.0
+    # inside a chunk the eight products are added in ascending d: 2^24, 1, 1 -> 2^24 (each 1 is lost), -2^24 last -> 0;
+    # with the two 1s first the sum would be 2
+    x[:], m[:] = 0.0, 0.0
+    x[0, 0], m[0, 0] = 4096.0, 4096.0
+    x[0, 1], m[0, 1] = 1.0, 1.0
+    x[0, 2], m[0, 2] = 1.0, 1.0
+    x[0, 3], m[0, 3] = -4096.0, 4096.0
+    assert oracle.route_scores(bf(x), bf(m))[0, 0] == 0.0
 
 
 def test_route_top1_brute_force_ties_and_cosine():
