@@ -136,6 +136,36 @@ int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_co
               const uint16_t* G, int64_t T, int64_t F, int64_t N, int V, int M, int out_f_major,
               uint16_t* out, void* workspace, size_t ws_bytes, void* stream);
 
+/* Section 3.3 / Alg. 3 ("Convert Activation to Venom") and the conversion steps 1-3 of Section 3.4: neuron-level
+ * experts that produce the V:N:M activation directly.  Reading built here: E = M/4 experts; expert e owns the hidden
+ * units f with (f mod M)/4 == e (the offline clustering is taken as already applied to W1's row order), so a block of
+ * 64 token rows routed to e keeps exactly the block columns 4e..4e+3; a token goes to one expert.
+ *
+ * venom_route = steps 1-2.  means [M/4, D] bf16 (unit-normalised offline, which makes the product below rank experts
+ * like the cosine similarity).  s[t,e] = sum_d X[t,d]*means[e,d] in fp32 with a fixed order (products in chunks of 8
+ * consecutive d; partial sum l of 64 takes chunks l, l+64, ... in ascending d; the partials are folded by 32, 16, 8,
+ * 4, 2, 1); expert[t] = argmax_e, ties to the lower e.  Then a stable grouping: tokens of one expert in ascending
+ * order, every run padded to a multiple of 64 rows.  Outputs (device): expert [T]; perm [rows] = token of a row or -1
+ * (padding), rows = sffn_venom_rows(T, M) = ceil64(T) + 64 M/4; row_of_token [T]; seg [M/4 + 1] int32 run offsets;
+ * scores [T, M/4] fp32 or NULL.  D a positive multiple of 8.  The caller copies seg to the host for the next call. */
+int64_t sffn_venom_rows(int64_t T, int M);
+size_t  sffn_venom_route_workspace_bytes(int64_t T, int M);
+int venom_route(const uint16_t* X, const uint16_t* means, int64_t T, int64_t D, int M, int32_t* expert,
+                int32_t* perm, int32_t* row_of_token, int32_t* seg, float* scores, void* workspace,
+                size_t ws_bytes, void* stream);
+
+/* venom_expert_matmul = step 3, the batched matmul that emits V:N:M: for row r of expert e's run and compact column j
+ * (hidden unit f = (j/4) M + 4e + j%4): y1c[r,j] = bf16( sum_d X[perm[r],d] * W1s[f,d] + b1[f] ), W1s = sparsify24(W1)
+ * (Alg. 1 line 4, cfg->mode); then eq. (2) and the 2:4 rule of Section 2.3 on every four consecutive compact columns.
+ * cfg: T tokens, D, F, V = 64, M; seg_offsets: HOST array [M/4 + 1] as produced by venom_route (validated here);
+ * outputs over rows = sffn_venom_rows(T, M): vals [rows, 2F/M], meta [rows, F/(2M)], colidx [rows/64, F/M, 4] in the
+ * packed layout above (padding rows are +0), y1c [rows, 4F/M] or NULL.  4F/M must be a multiple of 64.  One grouped
+ * launch on the structured-sparse matrix cores; (vals, meta, colidx) feed vnm_spmm / vnm_wgrad / dsqrelu_vnm as is. */
+size_t sffn_venom_matmul_workspace_bytes(int64_t T, int64_t D, int64_t F, int M);
+int venom_expert_matmul(const sffn_cfg* cfg, const int64_t* seg_offsets, const uint16_t* X, const int32_t* perm,
+                        const uint16_t* W1, const float* b1, uint16_t* y1c, uint16_t* vals, uint8_t* meta,
+                        uint8_t* colidx, void* workspace, size_t ws_bytes, void* stream);
+
 /* Alg. 1 + Alg. 2, one call: X [T,D], W1 [F,D], W2 [D,F], b1 fp32 [F] or NULL, dY [T,D] ->
  * Y3 [T,D], dX [T,D], dW1 [F,D], dW2 [D,F]; intermediates land in `workspace` at the offsets of
  * sffn_workspace_layout().  Both weight matrices are re-pruned inside the call.

@@ -63,6 +63,14 @@ def load():
     lib.sffn_grouped_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg), i32]
     lib.sffn_grouped_workspace_layout.argtypes = [ctypes.POINTER(_Cfg), i32, ctypes.POINTER(_Layout)]
     lib.ffn_sparse_step_grouped.argtypes = [ctypes.POINTER(_Cfg), i32, ctypes.POINTER(ctypes.c_int64)] + [p] * 9 + [p, sz, p]
+    lib.sffn_venom_rows.restype = i64
+    lib.sffn_venom_rows.argtypes = [i64, i32]
+    lib.sffn_venom_route_workspace_bytes.restype = sz
+    lib.sffn_venom_route_workspace_bytes.argtypes = [i64, i32]
+    lib.venom_route.argtypes = [p, p, i64, i64, i32, p, p, p, p, p, p, sz, p]
+    lib.sffn_venom_matmul_workspace_bytes.restype = sz
+    lib.sffn_venom_matmul_workspace_bytes.argtypes = [i64, i64, i64, i32]
+    lib.venom_expert_matmul.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(ctypes.c_int64)] + [p] * 8 + [p, sz, p]
     lib.sffn_profile_enable.argtypes = [i32]
     lib.sffn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_char_p), i32]
     _LIB = lib
@@ -281,3 +289,49 @@ def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD, keep_dense=True, M=8):
     step = FfnStep(T, D, F, mode, X.device, keep_dense, M)
     out = step(X, W1, W2, b1, dY)
     return out, step
+
+
+def venom_route(X, means, M, want_scores=False):
+    """Steps 1-2 of Section 3.3: top-1 expert per token and the stable, 64-row padded grouping.
+    -> dict(expert [T] i32, perm [rows] i32, row_of_token [T] i32, seg (host list, M/4 + 1), scores [T, M/4] f32 or None).
+    Reading seg back synchronises with the stream (the next call sizes its launch from it)."""
+    T, D = X.shape
+    E = M // 4
+    rows = load().sffn_venom_rows(T, M)
+    dev = X.device
+    i32t = lambda n: torch.empty((n,), dtype=torch.int32, device=dev)
+    expert, perm, row_of_token, seg = i32t(T), i32t(rows), i32t(T), i32t(E + 4)
+    scores = torch.empty((T, E), dtype=torch.float32, device=dev) if want_scores else None
+    nbytes = load().sffn_venom_route_workspace_bytes(T, M)
+    ws = _u8((max(nbytes, 16),), dev)
+    _check(load().venom_route(_ptr(X), _ptr(means), T, D, M, _ptr(expert), _ptr(perm), _ptr(row_of_token), _ptr(seg), _ptr(scores),
+                              _ptr(ws), nbytes, _stream()))
+    return dict(expert=expert, perm=perm, row_of_token=row_of_token, seg=[int(v) for v in seg[:E + 1].cpu()], scores=scores)
+
+
+def venom_expert_matmul(X, perm, seg, W1, b1, M, mode=MODE_HARD, keep_y1c=True, workspace=None):
+    """Step 3 of Section 3.3: the grouped matmul that emits V:N:M.  -> (vals, meta, colidx, y1c or None) over
+    sffn_venom_rows(T, M) rows."""
+    T, D = X.shape
+    F = W1.shape[0]
+    E = M // 4
+    rows = load().sffn_venom_rows(T, M)
+    dev = X.device
+    vals, meta = _bf16((rows, 2 * F // M), dev), _u8((rows, F // (2 * M)), dev)
+    colidx = _u8((rows // 64, F // M, 4), dev)
+    y1c = _bf16((rows, 4 * F // M), dev) if keep_y1c else None
+    nbytes = load().sffn_venom_matmul_workspace_bytes(T, D, F, M)
+    ws = workspace if workspace is not None else _u8((max(nbytes, 16),), dev)
+    c = _cfg(T, D, F, mode, M=M)
+    seg_arr = (ctypes.c_int64 * (E + 1))(*[int(v) for v in seg])
+    _check(load().venom_expert_matmul(ctypes.byref(c), seg_arr, _ptr(X), _ptr(perm), _ptr(W1), _ptr(b1), _ptr(y1c), _ptr(vals), _ptr(meta),
+                                      _ptr(colidx), _ptr(ws), nbytes, _stream()))
+    return vals, meta, colidx, y1c
+
+
+def moe_to_venom(X, W1, b1, means, M, mode=MODE_HARD):
+    """Alg. 3: route, permute, grouped matmul.  -> dict(expert, perm, row_of_token, seg, vals, meta, colidx, y1c)."""
+    r = venom_route(X, means, M)
+    vals, meta, colidx, y1c = venom_expert_matmul(X, r["perm"], r["seg"], W1, b1, M, mode)
+    r.update(vals=vals, meta=meta, colidx=colidx, y1c=y1c)
+    return r

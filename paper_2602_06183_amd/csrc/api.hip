@@ -237,6 +237,90 @@ int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_co
     return SFFN_OK;
 }
 
+// ---- Section 3.3 / Alg. 3: neuron-level experts that emit the V:N:M format ----------------------------------------
+int64_t sffn_venom_rows(int64_t T, int M) {
+    if (T < 0 || !vnm_ok(64, M)) return 0;
+    return (T + 63) / 64 * 64 + 64 * (M / 4);
+}
+
+size_t sffn_venom_route_workspace_bytes(int64_t T, int M) {
+    const int64_t cap = sffn_venom_rows(T, M);
+    if (cap == 0) return 0;
+    return up256((size_t)((cap + 1023) / 1024) * (M / 4) * sizeof(int32_t));
+}
+
+int venom_route(const uint16_t* X, const uint16_t* means, int64_t T, int64_t D, int M, int32_t* expert, int32_t* perm,
+                int32_t* row_of_token, int32_t* seg, float* scores, void* workspace, size_t ws_bytes, void* stream) {
+    REQUIRE(X && means && expert && perm && row_of_token && seg, SFFN_EINVAL, "venom_route: null pointer");
+    REQUIRE(vnm_ok(64, M), SFFN_EUNSUPPORTED, "venom_route: M must be 8, 16, 32 or 64 (M / 4 experts)");
+    REQUIRE(T > 0 && D > 0 && D % 8 == 0, SFFN_EINVAL, "venom_route: T must be positive and D a positive multiple of 8");
+    REQUIRE(fits_int(T) && fits_int(D) && T < 65536 * 64, SFFN_EUNSUPPORTED, "venom_route: dimension too large");
+    REQUIRE(aligned16(X) && aligned16(means) && aligned16(expert) && aligned16(perm) && aligned16(row_of_token) && aligned16(seg) &&
+                aligned16(scores) && aligned16(workspace), SFFN_EINVAL, "venom_route: pointers must be 16-byte aligned");
+    REQUIRE(workspace && ws_bytes >= sffn_venom_route_workspace_bytes(T, M), SFFN_EWORKSPACE, "venom_route: workspace missing or too small");
+    hipStream_t s = (hipStream_t)stream;
+    const int E = M / 4;
+    LAUNCH(launch_venom_route(X, means, T, D, E, expert, scores, s), "venom_route/scores");
+    LAUNCH(launch_venom_permute(expert, T, E, sffn_venom_rows(T, M), (int32_t*)workspace, seg, perm, row_of_token, s), "venom_route/permute");
+    return SFFN_OK;
+}
+
+size_t sffn_venom_matmul_workspace_bytes(int64_t T, int64_t D, int64_t F, int M) {
+    const int64_t cap = sffn_venom_rows(T, M);
+    if (cap == 0 || !mult64(D) || !mult64(F) || (4 * F / M) % 64 != 0) return 0;
+    // permuted X (blocked) + the expert-major packed W1: canonical and blocked copies
+    return up256((size_t)cap * D * 2) + 2 * (up256((size_t)F * D) + up256((size_t)F * D / 8));
+}
+
+int venom_expert_matmul(const sffn_cfg* cfg, const int64_t* seg_offsets, const uint16_t* X, const int32_t* perm, const uint16_t* W1,
+                        const float* b1, uint16_t* y1c, uint16_t* vals, uint8_t* meta, uint8_t* colidx, void* workspace, size_t ws_bytes,
+                        void* stream) {
+    REQUIRE(cfg && seg_offsets && X && perm && W1 && vals && meta && colidx, SFFN_EINVAL, "venom_expert_matmul: null pointer");
+    REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "venom_expert_matmul: only V=64 with M in {8, 16, 32, 64} is built");
+    const int64_t T = cfg->T, D = cfg->D, F = cfg->F;
+    const int M = cfg->M, E = M / 4;
+    REQUIRE(T > 0 && mult64(D) && mult64(F), SFFN_EINVAL, "venom_expert_matmul: T must be positive, D and F positive multiples of 64");
+    const int64_t Kc = 4 * F / M, cap = sffn_venom_rows(T, M);
+    REQUIRE(Kc % 64 == 0, SFFN_EINVAL, "venom_expert_matmul: 4 F / M (hidden units per expert) must be a multiple of 64");
+    REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "venom_expert_matmul: unknown mode");
+    REQUIRE(cap < 65536 * 64 && fits_int(F) && fits_int(D) && fits_int(cap * (D / 8)), SFFN_EUNSUPPORTED, "venom_expert_matmul: dimension too large");
+    REQUIRE(aligned16(X) && aligned16(perm) && aligned16(W1) && aligned16(b1) && aligned16(y1c) && aligned16(vals) && aligned16(meta) &&
+                aligned16(colidx) && aligned16(workspace), SFFN_EINVAL, "venom_expert_matmul: pointers must be 16-byte aligned");
+    REQUIRE(workspace && ws_bytes >= sffn_venom_matmul_workspace_bytes(T, D, F, M), SFFN_EWORKSPACE,
+            "venom_expert_matmul: workspace missing or too small");
+    GemmGroup g;
+    g.n = E; g.role = 1;
+    REQUIRE(seg_offsets[0] == 0 && seg_offsets[E] <= cap, SFFN_EINVAL, "venom_expert_matmul: seg_offsets must start at 0 and end within the row capacity");
+    for (int e = 0; e < E; ++e)
+        REQUIRE(seg_offsets[e + 1] >= seg_offsets[e] && seg_offsets[e + 1] % 64 == 0, SFFN_EINVAL,
+                "venom_expert_matmul: seg_offsets must be ascending multiples of 64");
+    for (int e = 0; e <= E; ++e) g.seg[e] = (int32_t)seg_offsets[e];
+    g.a_stride = Kc * D / 2; g.m_stride = Kc * D / 8; g.bias_stride = 4;
+
+    hipStream_t s = (hipStream_t)stream;
+    unsigned char* ws = (unsigned char*)workspace;
+    uint16_t* xb = (uint16_t*)ws;                      ws += up256((size_t)cap * D * 2);
+    uint16_t* wv = (uint16_t*)ws;                      ws += up256((size_t)F * D);
+    uint8_t* wm = ws;                                  ws += up256((size_t)F * D / 8);
+    uint16_t* wvb = (uint16_t*)ws;                     ws += up256((size_t)F * D);
+    uint8_t* wmb = ws;
+    LAUNCH(launch_venom_gather_x(X, perm, cap, D, xb, s), "venom_expert_matmul/gather(X)");
+    LAUNCH(launch_prune24_step(W1, F, D, D, 0, cfg->mode, wv, wm, wvb, wmb, nullptr, s, 1, M), "venom_expert_matmul/prune24(W1)");
+    LAUNCH(launch_venom_colidx(g, cap, F / M, colidx, s), "venom_expert_matmul/colidx");
+    // rows past the last run are never touched by the grouped contraction: clear them (they are padding)
+    if (seg_offsets[E] < cap) {
+        const int64_t rows = cap - seg_offsets[E];
+        LAUNCH(launch_fill_bytes(vals + seg_offsets[E] * (Kc / 2), 0, (size_t)rows * Kc, s), "venom_expert_matmul/clear");
+        LAUNCH(launch_fill_bytes(meta + seg_offsets[E] * (Kc / 8), 0x44, (size_t)rows * (Kc / 8), s), "venom_expert_matmul/clear");
+        if (y1c) LAUNCH(launch_fill_bytes(y1c + seg_offsets[E] * Kc, 0, (size_t)rows * Kc * 2, s), "venom_expert_matmul/clear");
+    }
+    VnmEpilogue ep;
+    ep.mode = 3; ep.store_dense = y1c ? 1 : 0; ep.vals = vals; ep.meta = meta; ep.perm = perm;
+    ep.logM = M == 8 ? 3 : M == 16 ? 4 : M == 32 ? 5 : 6;
+    LAUNCH(launch_gemm_vnm_epilogue(wvb, wmb, xb, b1, Kc, cap, D, y1c, ep, s, &g), "venom_expert_matmul/gemm");
+    return SFFN_OK;
+}
+
 // Alg. 1 + Alg. 2 for n_experts independent FFNs over consecutive token segments (n_experts = 1, seg = nullptr:
 // the plain step).  Every stage is one launch; the GEMMs find their expert from the segment table.
 static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, const uint16_t* X, const uint16_t* W1,

@@ -305,9 +305,16 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                     bb[a2][g] = make_float4(0.f, 0.f, 0.f, 0.f);
                     if (bias) {
                         int i = f0 + a2 * 32 + 8 * g + 4 * lh; i = i < Ra ? i : Ra - 4;
-                        bb[a2][g] = *reinterpret_cast<const float4*>(bias + i);
+                        // EPI 3: compact column i of the expert is hidden unit (i / 4) * M + 4 e + i % 4 (bias already points at 4 e)
+                        bb[a2][g] = *reinterpret_cast<const float4*>(EPI == 3 ? bias + ((int64_t)(i >> 2) << ep.logM) : bias + i);
                     }
                 }
+            bool tok_ok[FN];                                   // EPI 3: padding rows of the permuted token order come out as zeros
+#pragma unroll
+            for (int b = 0; b < FN; ++b) {
+                tok_ok[b] = true;
+                if (EPI == 3) { int j = t0 + b * 32 + l32; j = j < Rb ? j : Rb - 1; tok_ok[b] = ep.perm[j] >= 0; }
+            }
 #pragma unroll
             for (int a2 = 0; a2 < 2; ++a2)
 #pragma unroll
@@ -319,9 +326,9 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         const float v0 = acc[a][b][4 * g] + bb[a2][g].x, v1 = acc[a][b][4 * g + 1] + bb[a2][g].y;
                         const float v2 = acc[a][b][4 * g + 2] + bb[a2][g].z, v3 = acc[a][b][4 * g + 3] + bb[a2][g].w;
                         *reinterpret_cast<uint2*>(scratch + (b * 32 + l32) * EP + il * 2) =
-                            make_uint2(f2bf2(v0, v1), f2bf2(v2, v3));
+                            tok_ok[b] ? make_uint2(f2bf2(v0, v1), f2bf2(v2, v3)) : make_uint2(0u, 0u);
                     }
-            if (EPI != 0) {
+            if (EPI == 1 || EPI == 2) {
 #pragma unroll
                 for (int q = 0; q < (32 * EP + 1023) / 1024; ++q)
                     if ((q * 64 + lane) * 16 < 32 * EP) *reinterpret_cast<uint4*>(ttile + (q * 64 + lane) * 16) = make_uint4(0, 0, 0, 0);
@@ -336,7 +343,25 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         *reinterpret_cast<uint4*>(out + (int64_t)j * ldo + i) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
                 }
             }
-            if (EPI != 0) {
+            if (EPI == 3) {
+                // lane = (token t = lane / 16 + 4 it, group of four compact columns g = lane % 16): eq. (2), then the 2:4 rule
+                const int g = lane & 15;
+#pragma unroll
+                for (int it = 0; it < 16; ++it) {
+                    const int t = (lane >> 4) + 4 * it;
+                    const uint2 w = *reinterpret_cast<const uint2*>(scratch + t * EP + g * 8);
+                    uint32_t nib;
+                    const uint32_t v = select24<false>(sqrelu16(w.x & 0xFFFFu), sqrelu16(w.x >> 16), sqrelu16(w.y & 0xFFFFu), sqrelu16(w.y >> 16), nib);
+                    uint32_t mw = nib | (row_shl<1>(nib) << 4);            // metadata of 8 groups -> one 32-bit store from every eighth lane
+                    mw |= row_shl<2>(mw) << 8;
+                    mw |= row_shl<4>(mw) << 16;
+                    if (valid && t0 + t < Rb) {
+                        *reinterpret_cast<uint32_t*>(ep.vals + (int64_t)(t0 + t) * (F / 2) + (f0 >> 1) + 2 * g) = v;
+                        if ((g & 7) == 0) *reinterpret_cast<uint32_t*>(ep.meta + (int64_t)(t0 + t) * (F / 8) + (f0 >> 3) + (g >> 1)) = mw;
+                    }
+                }
+            }
+            if (EPI == 1 || EPI == 2) {
                 const int bl = lane & 7;                                  // column block handled in the per-row pass
                 const int64_t blk_g = (f0 >> 3) + bl;
                 uint32_t cw;                                              // the four kept column offsets of block bl
@@ -517,6 +542,9 @@ hipError_t launch_gemm_vnm_epilogue(const uint16_t* a_vals, const uint8_t* a_met
     dim3 grid(tiles);
     if (ep.mode == 0)       // no V:N:M work: the dense output only
         hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 0, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
+                           tiles_m, tiles_n, ep, g);
+    else if (ep.mode == 3)
+        hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 3, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
                            tiles_m, tiles_n, ep, g);
     else if (ep.mode == 1)
         hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 1, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,

@@ -24,6 +24,11 @@ struct VnmEpilogue {
     uint16_t* v24 = nullptr;
     uint8_t* m24 = nullptr;
     uint16_t* at = nullptr;
+    // mode 3 (Section 3.3, neuron-level experts; grouped launch, A = one expert's hidden units in compact-column order):
+    //        the tile of y1c gets the bias of its hidden units, is squared-ReLU'd and 2:4-pruned on every four consecutive
+    //        compact columns: outputs vals, meta; padding rows (perm < 0) come out as zeros; `out` = y1c [rows, F] if store_dense.
+    const int32_t* perm = nullptr;
+    int logM = 3;
 };
 
 // Grouped (mixture-of-experts) form of a contraction: the token axis is cut into n consecutive segments, one per
@@ -51,7 +56,8 @@ hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uin
 // trans = 1 can also emit a blocked copy of the source matrix itself (rows = its rows, K = its columns).
 // batch > 1 (trans = 1 only): `batch` matrices of the same shape, consecutive in every argument.
 hipError_t launch_prune24_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
-                               uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream, int batch = 1);
+                               uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream, int batch = 1,
+                               int cluster_M = 0);   // cluster_M (trans = 0): rows come out expert-major, see prune24.hip
 // Wider blocks, M in {16, 32, 64} (vnm_general.hip): same operations and packed layout as the M = 8 kernels.
 hipError_t launch_sqrelu_vnm_compress_m(const uint16_t* y1, int64_t T, int64_t F, int M, uint16_t* vals, uint8_t* meta, uint8_t* colidx,
                                         hipStream_t s);
@@ -94,6 +100,15 @@ hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a
 // eqs. (5), (8): C[f, n] = sum_t A[t, f] * G[t, n] with A given as `atc` (compacted transposed activation written by the
 // V:N:M epilogue) + kmask (kept-column bit masks, [T / 64, F / 8]), G = [N rows, T] in the blocked layout; out_i_contig: out[n * ldo + f], else out[f * ldo + n].
 // grp (role 2): every expert contracts over its own token segment into its own output (out_stride).
+// Section 3.3 / Alg. 3 (router.hip): routing scores + top-1, stable grouping by expert, permuted X, colidx of the result.
+hipError_t launch_venom_route(const uint16_t* X, const uint16_t* means, int64_t T, int64_t D, int E, int32_t* expert, float* scores,
+                              hipStream_t s);
+hipError_t launch_venom_permute(const int32_t* expert, int64_t T, int E, int64_t cap, int32_t* blockcnt, int32_t* seg, int32_t* perm,
+                                int32_t* row_of_token, hipStream_t s);
+hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, hipStream_t s);
+hipError_t launch_fill_bytes(void* p, uint8_t v, size_t n_bytes, hipStream_t s);
+hipError_t launch_venom_colidx(const GemmGroup& g, int64_t cap, int64_t groups, uint8_t* colidx, hipStream_t s);
+
 hipError_t launch_wgrad_vnm(const uint16_t* atc, const uint8_t* kmask, const uint16_t* G, int64_t F, int64_t N, int64_t T,
                             int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 

@@ -101,17 +101,21 @@ __global__ void __launch_bounds__(256) prune24_cols_kernel(const uint16_t* __res
 
 // Rows K-contiguous, fused-step variant: a wavefront owns 16 rows x 64 k, i.e. exactly one 1 KB block of the
 // blocked packed output; lane = (row, 16 k), two 16-byte loads, one 16-byte store per output.
+// logM > 0 (neuron-level experts, Section 3.3): output row e * Kc + j takes source row (j / 4) * M + 4 e + j % 4, i.e.
+// the rows of every expert's hidden units come out consecutively (expert-major), ready for one grouped contraction.
 template <bool SOFT>
 __global__ void __launch_bounds__(256) prune24_rows_step_kernel(const uint16_t* __restrict__ src, int K, int64_t ld,
                                                                uint16_t* __restrict__ vals, uint8_t* __restrict__ meta,
-                                                               uint16_t* __restrict__ vblk, uint8_t* __restrict__ mblk) {
+                                                               uint16_t* __restrict__ vblk, uint8_t* __restrict__ mblk, int logM, int Kc) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int chunk = blockIdx.x * 4 + wave;            // 64-k column
     if (chunk * 64 >= K) return;
     const int64_t r = (int64_t)blockIdx.y * 16 + (lane >> 2);
+    int64_t rs = r;                                     // source row
+    if (logM) { const int e = (int)(r / Kc), j = (int)(r - (int64_t)e * Kc); rs = ((int64_t)(j >> 2) << logM) + 4 * e + (j & 3); }
     const int q = lane & 3, k = chunk * 64 + 16 * q;
-    const uint4 w0 = *reinterpret_cast<const uint4*>(src + r * ld + k);
-    const uint4 w1 = *reinterpret_cast<const uint4*>(src + r * ld + k + 8);
+    const uint4 w0 = *reinterpret_cast<const uint4*>(src + rs * ld + k);
+    const uint4 w1 = *reinterpret_cast<const uint4*>(src + rs * ld + k + 8);
     uint32_t n0, n1, n2, n3;
     const uint32_t o0 = select24<SOFT>(w0.x & 0xFFFFu, w0.x >> 16, w0.y & 0xFFFFu, w0.y >> 16, n0);
     const uint32_t o1 = select24<SOFT>(w0.z & 0xFFFFu, w0.z >> 16, w0.w & 0xFFFFu, w0.w >> 16, n1);
@@ -148,12 +152,15 @@ hipError_t launch_prune24(const uint16_t* src, int64_t R, int64_t K, int64_t ld,
 }
 
 hipError_t launch_prune24_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
-                               uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream, int batch) {
+                               uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream, int batch, int cluster_M) {
     if (batch > 1 && (!trans || ld != R)) return hipErrorInvalidValue;
+    if (cluster_M && (trans || (cluster_M != 8 && cluster_M != 16 && cluster_M != 32 && cluster_M != 64) || R % cluster_M)) return hipErrorInvalidValue;
     if (!trans) {
         dim3 grid((unsigned)((K / 64 + 3) / 4), (unsigned)(R / 16));
-        if (mode == 0) hipLaunchKernelGGL((prune24_rows_step_kernel<false>), grid, dim3(256), 0, stream, src, (int)K, ld, vals, meta, vblk, mblk);
-        else           hipLaunchKernelGGL((prune24_rows_step_kernel<true>), grid, dim3(256), 0, stream, src, (int)K, ld, vals, meta, vblk, mblk);
+        const int logM = cluster_M == 8 ? 3 : cluster_M == 16 ? 4 : cluster_M == 32 ? 5 : cluster_M == 64 ? 6 : 0;
+        const int Kc = cluster_M ? (int)(4 * R / cluster_M) : 0;
+        if (mode == 0) hipLaunchKernelGGL((prune24_rows_step_kernel<false>), grid, dim3(256), 0, stream, src, (int)K, ld, vals, meta, vblk, mblk, logM, Kc);
+        else           hipLaunchKernelGGL((prune24_rows_step_kernel<true>), grid, dim3(256), 0, stream, src, (int)K, ld, vals, meta, vblk, mblk, logM, Kc);
     } else {
         dim3 grid((unsigned)(R / 64), (unsigned)((K + 127) / 128), (unsigned)batch);
         if (mode == 0) hipLaunchKernelGGL((prune24_cols_kernel<false>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta, vblk, mblk, src_blk);

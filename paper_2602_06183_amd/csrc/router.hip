@@ -1,0 +1,211 @@
+// Neuron-level router of Section 3.3 / Alg. 3, steps 1 and 2 of the conversion listed in Section 3.4, and the small
+// data-movement kernels of step 3:
+//   route:   s[t, e] = x[t] . mean[e] (float32, fixed summation order), expert[t] = argmax_e (ties to the lower e)
+//   permute: stable grouping of the tokens by expert, every run padded to 64 rows (perm, row_of_token, seg)
+//   gather:  X rows in permuted order, written in the blocked operand layout; colidx of the V:N:M result
+// HBM-bound: the route kernel reads X once (16 bytes per lane), the others move indices and one copy of X.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace sffn {
+
+// One wavefront scores TOK tokens against all E experts.  Summation order (part of the parity contract, the argmax
+// depends on it): the products are cut into chunks of 8 consecutive d; lane l accumulates chunks l, l + 64, ... in
+// ascending d, then the 64 partial sums are folded by 32, 16, 8, 4, 2, 1.  A bf16 x bf16 product is exact in
+// float32, so fmaf rounds exactly like the separate add.
+template <int E, int TOK>
+__global__ void __launch_bounds__(256) venom_route_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ means, int T, int D,
+                                                         int32_t* __restrict__ expert, float* __restrict__ scores) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t0 = (blockIdx.x * 4 + wave) * TOK;
+    if (t0 >= T) return;
+    float acc[TOK][E];
+#pragma unroll
+    for (int q = 0; q < TOK; ++q)
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[q][e] = 0.0f;
+    for (int d = lane * 8; d < D; d += 512) {
+        uint4 mv[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) mv[e] = *reinterpret_cast<const uint4*>(means + (int64_t)e * D + d);
+#pragma unroll
+        for (int q = 0; q < TOK; ++q) {
+            const int t = t0 + q < T ? t0 + q : T - 1;
+            const uint4 xv = *reinterpret_cast<const uint4*>(X + (int64_t)t * D + d);
+            const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const uint32_t mw[4] = {mv[e].x, mv[e].y, mv[e].z, mv[e].w};
+                float a = acc[q][e];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    a = __builtin_fmaf(bf2f(xw[k] & 0xFFFFu), bf2f(mw[k] & 0xFFFFu), a);
+                    a = __builtin_fmaf(bf2f(xw[k] >> 16), bf2f(mw[k] >> 16), a);
+                }
+                acc[q][e] = a;
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < TOK; ++q) {
+        float best = 0.0f;
+        int arg = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            float s = acc[q][e];
+#pragma unroll
+            for (int w = 32; w >= 1; w >>= 1) s = s + __shfl_xor(s, w, 64);     // both partners add the same two numbers
+            if (e == 0 || s > best) { best = s; arg = e; }
+            if (scores && lane == 0 && t0 + q < T) scores[(int64_t)(t0 + q) * E + e] = s;
+        }
+        if (lane == 0 && t0 + q < T) expert[t0 + q] = arg;
+    }
+}
+
+// ---- stable grouping by expert ------------------------------------------------------------------------------------
+// Pass 1: per block of 1024 tokens, how many go to each expert; also clears perm to -1 (padding).
+__global__ void __launch_bounds__(256) venom_count_kernel(const int32_t* __restrict__ expert, int T, int E, int cap,
+                                                         int32_t* __restrict__ blockcnt, int32_t* __restrict__ perm) {
+    __shared__ int cnt[16];
+    if (threadIdx.x < 16) cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const int base = blockIdx.x * 1024;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int t = base + k * 256 + threadIdx.x;
+        if (t < cap) perm[t] = -1;
+        if (t < T) atomicAdd(&cnt[expert[t]], 1);            // integer counts: the result does not depend on the order
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < E) blockcnt[blockIdx.x * E + threadIdx.x] = cnt[threadIdx.x];
+}
+
+// Pass 2 (one workgroup): first row of every (block, expert) and the 64-row padded run offsets.
+__global__ void __launch_bounds__(64) venom_scan_kernel(int32_t* __restrict__ blockcnt, int nblk, int E, int32_t* __restrict__ seg) {
+    __shared__ int total[16];
+    const int e = threadIdx.x;
+    if (e < E) {
+        int run = 0;
+        for (int b = 0; b < nblk; ++b) {
+            const int c = blockcnt[b * E + e];
+            blockcnt[b * E + e] = run;                        // becomes: tokens of expert e in earlier blocks
+            run += c;
+        }
+        total[e] = run;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int off = 0;
+        seg[0] = 0;
+        for (int q = 0; q < E; ++q) { off += (total[q] + 63) & ~63; seg[q + 1] = off; }
+    }
+}
+
+// Pass 3: every token's row = seg[e] + tokens of e in earlier blocks + rank among the block's earlier tokens of e.
+__global__ void __launch_bounds__(256) venom_scatter_kernel(const int32_t* __restrict__ expert, int T, int E,
+                                                           const int32_t* __restrict__ blockbase, const int32_t* __restrict__ seg,
+                                                           int32_t* __restrict__ perm, int32_t* __restrict__ row_of_token) {
+    __shared__ int run[16];
+    __shared__ int wcnt[4][16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if ((int)threadIdx.x < E) run[threadIdx.x] = seg[threadIdx.x] + blockbase[blockIdx.x * E + threadIdx.x];
+    __syncthreads();
+    const int base = blockIdx.x * 1024;
+    for (int k = 0; k < 4; ++k) {
+        const int t = base + k * 256 + threadIdx.x;
+        const int e = t < T ? expert[t] : -1;
+        int rank = 0;
+        for (int q = 0; q < E; ++q) {                         // E <= 16 ballots: rank among the wave's earlier lanes of the same expert
+            const unsigned long long m = __ballot(e == q);
+            if (e == q) rank = __popcll(m & ((1ull << lane) - 1ull));
+            if (lane == 0) wcnt[wave][q] = __popcll(m);
+        }
+        __syncthreads();
+        if (e >= 0) {
+            int r = run[e] + rank;
+            for (int w = 0; w < wave; ++w) r += wcnt[w][e];
+            perm[r] = t;
+            row_of_token[t] = r;
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < E) run[threadIdx.x] += wcnt[0][threadIdx.x] + wcnt[1][threadIdx.x] + wcnt[2][threadIdx.x] + wcnt[3][threadIdx.x];
+        __syncthreads();
+    }
+}
+
+// X rows in permuted order (zero rows for padding), blocked operand layout: one thread per 16 bytes.
+__global__ void __launch_bounds__(256) venom_gather_x_kernel(const uint16_t* __restrict__ X, const int32_t* __restrict__ perm, int cap, int D,
+                                                            uint16_t* __restrict__ xb) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int cpr = D >> 3;
+    const int64_t r = idx / cpr;
+    const int c = (int)(idx - r * cpr);
+    if (r >= cap) return;
+    const int t = perm[r];
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (t >= 0) v = *reinterpret_cast<const uint4*>(X + (int64_t)t * D + c * 8);
+    *reinterpret_cast<uint4*>(xb + blk_off(r, c * 8, D >> 5)) = v;
+}
+
+// colidx[tb, g, :] = (4e, 4e + 1, 4e + 2, 4e + 3) for the 64-row blocks of expert e's run; blocks past the last run: e = 0.
+__global__ void __launch_bounds__(256) venom_colidx_kernel(GemmGroup g, int nblocks, int groups, uint32_t* __restrict__ colidx) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)nblocks * groups) return;
+    const int tb = (int)(idx / groups);
+    int e = 0;
+    for (int q = 0; q < g.n; ++q)
+        if (tb * 64 >= g.seg[q] && tb * 64 < g.seg[q + 1]) e = q;
+    colidx[idx] = 0x03020100u + 0x04040404u * (uint32_t)e;
+}
+
+__global__ void __launch_bounds__(256) fill_words_kernel(uint32_t* __restrict__ p, uint32_t v, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// n_bytes (a multiple of 4) bytes at p <- byte value v; a kernel rather than a memset node, so that callers may capture it
+hipError_t launch_fill_bytes(void* p, uint8_t v, size_t n_bytes, hipStream_t s) {
+    if (n_bytes == 0) return hipSuccess;
+    const int64_t n = (int64_t)(n_bytes / 4);
+    hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (uint32_t*)p, 0x01010101u * v, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_venom_route(const uint16_t* X, const uint16_t* means, int64_t T, int64_t D, int E, int32_t* expert, float* scores,
+                              hipStream_t s) {
+    if (T == 0) return hipSuccess;
+    constexpr int TOK = 8;
+    dim3 grid((unsigned)((T + 4 * TOK - 1) / (4 * TOK)));
+    switch (E) {
+        case 2:  hipLaunchKernelGGL((venom_route_kernel<2, TOK>), grid, dim3(256), 0, s, X, means, (int)T, (int)D, expert, scores); break;
+        case 4:  hipLaunchKernelGGL((venom_route_kernel<4, TOK>), grid, dim3(256), 0, s, X, means, (int)T, (int)D, expert, scores); break;
+        case 8:  hipLaunchKernelGGL((venom_route_kernel<8, TOK>), grid, dim3(256), 0, s, X, means, (int)T, (int)D, expert, scores); break;
+        case 16: hipLaunchKernelGGL((venom_route_kernel<16, 4>), dim3((unsigned)((T + 15) / 16)), dim3(256), 0, s, X, means, (int)T, (int)D, expert, scores); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_venom_permute(const int32_t* expert, int64_t T, int E, int64_t cap, int32_t* blockcnt, int32_t* seg, int32_t* perm,
+                                int32_t* row_of_token, hipStream_t s) {
+    const int nblk = (int)((cap + 1023) / 1024);
+    hipLaunchKernelGGL(venom_count_kernel, dim3(nblk), dim3(256), 0, s, expert, (int)T, E, (int)cap, blockcnt, perm);
+    hipLaunchKernelGGL(venom_scan_kernel, dim3(1), dim3(64), 0, s, blockcnt, nblk, E, seg);
+    hipLaunchKernelGGL(venom_scatter_kernel, dim3(nblk), dim3(256), 0, s, expert, (int)T, E, blockcnt, seg, perm, row_of_token);
+    return hipGetLastError();
+}
+
+hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, hipStream_t s) {
+    const int64_t n = cap * (D / 8);
+    hipLaunchKernelGGL(venom_gather_x_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, X, perm, (int)cap, (int)D, xb);
+    return hipGetLastError();
+}
+
+hipError_t launch_venom_colidx(const GemmGroup& g, int64_t cap, int64_t groups, uint8_t* colidx, hipStream_t s) {
+    const int64_t n = (cap / 64) * groups;
+    hipLaunchKernelGGL(venom_colidx_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, g, (int)(cap / 64), (int)groups,
+                       reinterpret_cast<uint32_t*>(colidx));
+    return hipGetLastError();
+}
+
+}  // namespace sffn

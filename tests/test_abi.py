@@ -82,6 +82,33 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     assert lib.sffn_grouped_workspace_bytes(ctypes.byref(cfg), 0) == 0
 
 
+def test_router_entry_points_validate_on_the_host():
+    lib = sffn.load()
+    fake = ctypes.c_void_p(0x1000)
+    assert lib.sffn_venom_rows(100, 16) == 128 + 64 * 4 and lib.sffn_venom_rows(8192, 8) == 8192 + 128
+    assert lib.sffn_venom_rows(100, 12) == 0
+    assert lib.sffn_venom_route_workspace_bytes(100, 16) >= 4 * 4
+    assert lib.venom_route(fake, fake, 100, 64, 12, fake, fake, fake, fake, None, fake, 1 << 20, None) == -2     # M / 4 experts
+    assert lib.venom_route(fake, fake, 100, 60, 16, fake, fake, fake, fake, None, fake, 1 << 20, None) == -1     # D not a multiple of 8
+    assert lib.venom_route(fake, fake, 100, 64, 16, fake, fake, fake, fake, None, fake, 0, None) == -3
+    assert lib.venom_route(fake, None, 100, 64, 16, fake, fake, fake, fake, None, fake, 1 << 20, None) == -1
+    cfg = binding._Cfg(100, 64, 1024, 64, 16, 0, 0)
+    seg = lambda *v: (ctypes.c_int64 * len(v))(*v)
+    big = 1 << 40
+    ok = seg(0, 64, 128, 128, 192)
+    tail = [fake] * 8
+    assert lib.sffn_venom_matmul_workspace_bytes(100, 64, 1024, 16) > 0
+    assert lib.sffn_venom_matmul_workspace_bytes(100, 64, 640, 16) == 0                                          # 4 F / M not a multiple of 64
+    assert lib.venom_expert_matmul(ctypes.byref(cfg), ok, *tail, fake, 16, None) == -3
+    assert lib.venom_expert_matmul(ctypes.byref(cfg), None, *tail, fake, big, None) == -1
+    assert lib.venom_expert_matmul(ctypes.byref(cfg), seg(0, 64, 100, 128, 192), *tail, fake, big, None) == -1   # not a multiple of 64
+    assert lib.venom_expert_matmul(ctypes.byref(cfg), seg(0, 64, 128, 64, 192), *tail, fake, big, None) == -1    # descending
+    assert lib.venom_expert_matmul(ctypes.byref(cfg), seg(64, 64, 128, 128, 192), *tail, fake, big, None) == -1  # does not start at 0
+    assert lib.venom_expert_matmul(ctypes.byref(cfg), seg(0, 64, 128, 256, 448), *tail, fake, big, None) == -1   # beyond the row capacity (384)
+    bad = binding._Cfg(100, 64, 640, 64, 16, 0, 0)
+    assert lib.venom_expert_matmul(ctypes.byref(bad), ok, *tail, fake, big, None) == -1
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB", None)
     monkeypatch.setattr(binding, "_HERE", str(tmp_path))

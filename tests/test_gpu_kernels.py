@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2602_06183_amd as sffn
 from tests.util import to_dev, to_bits, assert_gemm_close
-from workload import make_ffn_inputs, make_moe_inputs, bf16_bits_from_f32
+from workload import make_ffn_inputs, make_moe_inputs, make_router_inputs, bf16_bits_from_f32
 
 pytestmark = pytest.mark.gpu
 
@@ -401,3 +401,52 @@ def test_ffn_sparse_step_wide_blocks(M, mode, F):
     _check_wide_step_against_oracle(inp, s, outs, mode, M)
     density = np.mean(oracle.vnm_decompress(s["y2_vals"], s["y2_meta"], s["colidx"], 64, M) != 0)
     assert density <= 2.0 / M + 1e-9                       # Table 5: sparsity at least 1 - N / M
+
+
+# ---- neuron-level router (Section 3.3, Alg. 3) -------------------------------------------------------------------
+
+@pytest.mark.parametrize("T,D,M", [(300, 192, 8), (1500, 256, 16), (2100, 1024, 32), (4096, 520, 64), (64, 64, 16), (1, 2048, 8)])
+def test_venom_route_matches_oracle_bit_for_bit(T, D, M):
+    """Steps 1-2: float32 scores in the stated order (bit-exact, so the argmax is too), stable 64-row padded grouping."""
+    inp = make_router_inputs(T, D, 256, M, seed=T + M)
+    r = sffn.venom_route(to_dev(inp["X"]), to_dev(inp["means"]), M, want_scores=True)
+    torch.cuda.synchronize()
+    s = oracle.route_scores(inp["X"], inp["means"])
+    assert np.array_equal(to_bits(r["scores"]).view(np.uint32), s.view(np.uint32))
+    expert = oracle.route_top1(s)
+    assert np.array_equal(to_bits(r["expert"]), expert)
+    perm, seg = oracle.expert_permutation(expert, M // 4)
+    assert r["seg"] == [int(v) for v in seg]
+    assert np.array_equal(to_bits(r["perm"]), perm)
+    rot = to_bits(r["row_of_token"])
+    assert np.array_equal(perm[rot], np.arange(T))
+
+
+def test_venom_route_ties_go_to_the_lower_expert():
+    X = bf16_bits_from_f32(np.ones((70, 64), dtype=np.float32))
+    means = bf16_bits_from_f32(np.tile(np.array([[0.5], [1.0], [1.0], [0.25]], dtype=np.float32), (1, 64)))
+    r = sffn.venom_route(to_dev(X), to_dev(means), 16)
+    assert np.all(to_bits(r["expert"]) == 1) and r["seg"] == [0, 0, 128, 128, 128]
+
+
+@pytest.mark.parametrize("M,mode,T,D,F", [(8, sffn.MODE_HARD, 700, 128, 512), (16, sffn.MODE_SOFT, 1000, 192, 1024),
+                                          (32, sffn.MODE_HARD, 333, 64, 2048), (64, sffn.MODE_HARD, 2000, 256, 1024)])
+def test_moe_to_venom_against_oracle(M, mode, T, D, F):
+    """Alg. 3 end to end, teacher-forced: routing and permutation bit-exact; the grouped matmul within the GEMM
+    tolerance of the oracle's on the same permutation; eq. (2) + 2:4 packing bit-exact from the GPU's own y1c; and
+    the result consumed by the activation GEMM (eq. (3)) like any other V:N:M matrix."""
+    inp = make_router_inputs(T, D, F, M, seed=M + T, zero_fraction=0.75)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    r = sffn.moe_to_venom(dev["X"], dev["W1"], dev["b1"], dev["means"], M, mode)
+    torch.cuda.synchronize()
+    expert = oracle.route_top1(oracle.route_scores(inp["X"], inp["means"]))
+    perm, seg = oracle.expert_permutation(expert, M // 4)
+    assert np.array_equal(to_bits(r["expert"]), expert) and np.array_equal(to_bits(r["perm"]), perm) and r["seg"] == [int(v) for v in seg]
+    y1c = to_bits(r["y1c"])
+    ref = oracle.expert_matmul(inp["X"], perm, seg, inp["W1"], inp["b1"], M, mode)
+    assert not y1c[perm < 0].any()
+    assert_gemm_close(y1c, ref, "y1c")
+    ov, om, oc = oracle.venom_from_compact(y1c, perm, seg, M)
+    assert np.array_equal(to_bits(r["colidx"]), oc) and np.array_equal(to_bits(r["meta"]), om) and np.array_equal(to_bits(r["vals"]), ov)
+    y3 = sffn.vnm_spmm(r["vals"], r["meta"], r["colidx"], dev["W2"], 0, 64, M)
+    assert_gemm_close(to_bits(y3), oracle.vnm_spmm(ov, om, oc, inp["W2"], 0, 64, M), "y3")
