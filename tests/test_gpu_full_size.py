@@ -203,3 +203,38 @@ def test_full_size_wide_block_step(M):
             sub_c[:, 1] = np.arange(4, dtype=np.uint8)
             a = oracle.bits_to_f64(oracle.vnm_decompress(sub_v, sub_m, sub_c, 64, M))[:, :M]
             assert_gemm_close(got, oracle.f64_to_bits(a.T @ oracle.bits_to_f64(G)), "wgrad columns")
+
+
+@pytest.mark.parametrize("M", [8, 32])
+def test_full_size_router(M):
+    """Alg. 3 at the 1B shape: routing and grouping bit-exact in full; the grouped matmul on sampled rows; eq. (2) + 2:4
+    packing bit-exact on sampled 64-row blocks from the GPU's own y1c; eq. (3) on the result on sampled rows."""
+    from workload import make_router_inputs
+    T, D, F = CONFIGS["1b"]
+    inp = make_router_inputs(T, D, F, M, seed=0)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    r = sffn.moe_to_venom(dev["X"], dev["W1"], dev["b1"], dev["means"], M)
+    y3 = sffn.vnm_spmm(r["vals"], r["meta"], r["colidx"], dev["W2"], 0, 64, M)
+    torch.cuda.synchronize()
+    expert = oracle.route_top1(oracle.route_scores(inp["X"], inp["means"]))
+    perm, seg = oracle.expert_permutation(expert, M // 4)
+    assert np.array_equal(to_bits(r["expert"]), expert) and np.array_equal(to_bits(r["perm"]), perm) and r["seg"] == [int(v) for v in seg]
+    counts = np.bincount(expert, minlength=M // 4)
+    assert counts.min() > 0 and counts.max() < 3 * T // (M // 4)          # uneven but not degenerate
+    y1c, vals, meta, colidx, y3 = (to_bits(t) for t in (r["y1c"], r["vals"], r["meta"], r["colidx"], y3))
+    rng = np.random.default_rng(77)
+    w1s = oracle.prune24_dense(inp["W1"])
+    Kc = 4 * F // M
+    for tb in sorted(set(int(b) for b in rng.choice(int(seg[-1]) // 64, 6, replace=False)) | {0, len(perm) // 64 - 1}):
+        rows = np.arange(64 * tb, 64 * tb + 64)
+        e = int(np.searchsorted(seg, 64 * tb, side="right") - 1) if 64 * tb < seg[-1] else 0
+        ov, om, oc = oracle.venom_from_compact(y1c[rows], perm[rows], np.clip(seg - 64 * tb, 0, 64), M)     # the runs as seen from this block
+        assert np.array_equal(colidx[tb:tb + 1], oc) and np.array_equal(meta[rows], om) and np.array_equal(vals[rows], ov)
+        real = rows[perm[rows] >= 0][:8]
+        if len(real):
+            ref = oracle.bits_to_f64(inp["X"][perm[real]]) @ oracle.bits_to_f64(w1s[oracle.cluster_rows(e, M, F)]).T
+            ref = oracle.f64_to_bits(ref + inp["b1"].astype(np.float64)[oracle.cluster_rows(e, M, F)][None, :])
+            assert_gemm_close(y1c[real], ref, "y1c rows")
+            dense = oracle.vnm_decompress(ov, om, oc, 64, M)
+            assert_gemm_close(y3[real], oracle.dense_nt(dense[real - 64 * tb], inp["W2"]), "y3 rows")
+        assert Kc == y1c.shape[1]

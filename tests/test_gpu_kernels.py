@@ -450,3 +450,22 @@ def test_moe_to_venom_against_oracle(M, mode, T, D, F):
     assert np.array_equal(to_bits(r["colidx"]), oc) and np.array_equal(to_bits(r["meta"]), om) and np.array_equal(to_bits(r["vals"]), ov)
     y3 = sffn.vnm_spmm(r["vals"], r["meta"], r["colidx"], dev["W2"], 0, 64, M)
     assert_gemm_close(to_bits(y3), oracle.vnm_spmm(ov, om, oc, inp["W2"], 0, 64, M), "y3")
+
+
+def test_moe_to_venom_with_empty_experts():
+    """All tokens choose one expert: the other runs are empty, the grouped launch covers one run, rows past it are padding."""
+    M, T, D, F = 16, 130, 64, 512
+    inp = make_router_inputs(T, D, F, M, seed=4, zero_fraction=0.5)
+    inp["X"] = bf16_bits_from_f32(np.abs(oracle.bits_to_f32(inp["X"])))
+    inp["means"] = bf16_bits_from_f32(np.tile(np.array([[0.01], [0.02], [0.125], [-1.0]], dtype=np.float32), (1, D)))
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    r = sffn.moe_to_venom(dev["X"], dev["W1"], dev["b1"], dev["means"], M)
+    torch.cuda.synchronize()
+    assert r["seg"] == [0, 0, 0, 192, 192] and np.all(to_bits(r["expert"]) == 2)
+    perm, seg = oracle.expert_permutation(to_bits(r["expert"]), 4)
+    assert np.array_equal(to_bits(r["perm"]), perm)
+    y1c = to_bits(r["y1c"])
+    assert_gemm_close(y1c, oracle.expert_matmul(inp["X"], perm, seg, inp["W1"], inp["b1"], M), "y1c")
+    ov, om, oc = oracle.venom_from_compact(y1c, perm, seg, M)
+    assert np.array_equal(to_bits(r["colidx"]), oc) and np.array_equal(to_bits(r["meta"]), om) and np.array_equal(to_bits(r["vals"]), ov)
+    assert not to_bits(r["vals"])[T:].any()
