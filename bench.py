@@ -226,6 +226,24 @@ def main():
             venom["64:2:%d" % m] = {"ms": round(t, 4), "speedup_vs_dense": round(t_dense / t, 3)}
         del dense_out
 
+    # ---- conversion to V:N:M by the neuron-level router (Section 3.3; the three steps whose cost Section 3.4 discusses):
+    #      routing (reads X once), stable grouping + gather of X, grouped matmul that emits V:N:M; E = M / 4 experts ----
+    router = None
+    if not moe:
+        from workload import make_router_inputs   # only the expert means are new; X, W1, b1 are the step's
+        router = {"dense_y1_ms": round(ms_of(lambda: torch.addmm(b1h, X, W1.t(), out=y1)), 4)}
+        for m in (8, 16, 32, 64):
+            means = dev(make_router_inputs(64, D, 4 * m, m, seed=0)["means"])
+            t_route = ms_of(lambda: sffn.venom_route_launch(X, means, m))
+            rr = sffn.venom_route(X, means, m)
+            ws_r = torch.empty((sffn.load().sffn_venom_matmul_workspace_bytes(T, D, F, m),), dtype=torch.uint8, device="cuda")
+            t_mm = ms_of(lambda: sffn.venom_expert_matmul(X, rr["perm"], rr["seg"], W1, b1, m, mode, keep_y1c=False, workspace=ws_r))
+            router["64:2:%d" % m] = {"experts": m // 4, "rows": int(rr["perm"].shape[0]), "route_and_group_ms": round(t_route, 4),
+                                     "route_and_group_GBs_of_X": round(T * D * 2 / (t_route * 1e-3) / 1e9, 1),
+                                     "gather_prune_matmul_ms": round(t_mm, 4),
+                                     "conversion_vs_dense_y1": round(router["dense_y1_ms"] / (t_route + t_mm), 3)}
+            del ws_r, rr, means
+
     # ---- how much of the activation's L1 mass the V:N:M format keeps (sum of kept y2 / sum of all y2): one extra,
     #      untimed step that also stores the dense y1; plain torch reductions, measurement only ------------------
     retained = None
@@ -279,6 +297,7 @@ def main():
         "standalone_kernels": kernels,
         "venom_gemm_microbench": venom,
         "gemm24_microbench": gemm24,
+        "router_conversion": router,
         "retained_l1_fraction": retained, "relu_zero_fraction": zero_frac,
         "roofline": roofline, "cpu_baseline": cpu,
         "paper_context": "paper reports 1.4-1.5x for 2:4 GEMMs and 1.4-1.7x end-to-end on NVIDIA sparse tensor cores (Sections 1, 5.2.3); context, not a target",

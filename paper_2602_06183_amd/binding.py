@@ -291,10 +291,8 @@ def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD, keep_dense=True, M=8):
     return out, step
 
 
-def venom_route(X, means, M, want_scores=False):
-    """Steps 1-2 of Section 3.3: top-1 expert per token and the stable, 64-row padded grouping.
-    -> dict(expert [T] i32, perm [rows] i32, row_of_token [T] i32, seg (host list, M/4 + 1), scores [T, M/4] f32 or None).
-    Reading seg back synchronises with the stream (the next call sizes its launch from it)."""
+def venom_route_launch(X, means, M, want_scores=False):
+    """venom_route without the read-back: seg stays a device tensor (int32, first M/4 + 1 entries)."""
     T, D = X.shape
     E = M // 4
     rows = load().sffn_venom_rows(T, M)
@@ -306,7 +304,16 @@ def venom_route(X, means, M, want_scores=False):
     ws = _u8((max(nbytes, 16),), dev)
     _check(load().venom_route(_ptr(X), _ptr(means), T, D, M, _ptr(expert), _ptr(perm), _ptr(row_of_token), _ptr(seg), _ptr(scores),
                               _ptr(ws), nbytes, _stream()))
-    return dict(expert=expert, perm=perm, row_of_token=row_of_token, seg=[int(v) for v in seg[:E + 1].cpu()], scores=scores)
+    return dict(expert=expert, perm=perm, row_of_token=row_of_token, seg=seg[:E + 1], scores=scores)
+
+
+def venom_route(X, means, M, want_scores=False):
+    """Steps 1-2 of Section 3.3: top-1 expert per token and the stable, 64-row padded grouping.
+    -> dict(expert [T] i32, perm [rows] i32, row_of_token [T] i32, seg (host list, M/4 + 1), scores [T, M/4] f32 or None).
+    Reading seg back synchronises with the stream (the next call sizes its launch from it)."""
+    r = venom_route_launch(X, means, M, want_scores)
+    r["seg"] = [int(v) for v in r["seg"].cpu()]
+    return r
 
 
 def venom_expert_matmul(X, perm, seg, W1, b1, M, mode=MODE_HARD, keep_y1c=True, workspace=None):

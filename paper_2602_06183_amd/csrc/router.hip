@@ -174,13 +174,14 @@ hipError_t launch_fill_bytes(void* p, uint8_t v, size_t n_bytes, hipStream_t s) 
 hipError_t launch_venom_route(const uint16_t* X, const uint16_t* means, int64_t T, int64_t D, int E, int32_t* expert, float* scores,
                               hipStream_t s) {
     if (T == 0) return hipSuccess;
-    constexpr int TOK = 8;
+    // two tokens per wavefront: enough wavefronts in flight to hide the load latency (8 tokens per wavefront: 1.2-2.2 TB/s of X)
+    constexpr int TOK = 2;
     dim3 grid((unsigned)((T + 4 * TOK - 1) / (4 * TOK)));
     switch (E) {
         case 2:  hipLaunchKernelGGL((venom_route_kernel<2, TOK>), grid, dim3(256), 0, s, X, means, (int)T, (int)D, expert, scores); break;
         case 4:  hipLaunchKernelGGL((venom_route_kernel<4, TOK>), grid, dim3(256), 0, s, X, means, (int)T, (int)D, expert, scores); break;
         case 8:  hipLaunchKernelGGL((venom_route_kernel<8, TOK>), grid, dim3(256), 0, s, X, means, (int)T, (int)D, expert, scores); break;
-        case 16: hipLaunchKernelGGL((venom_route_kernel<16, 4>), dim3((unsigned)((T + 15) / 16)), dim3(256), 0, s, X, means, (int)T, (int)D, expert, scores); break;
+        case 16: hipLaunchKernelGGL((venom_route_kernel<16, 4>), dim3((unsigned)((T + 15) / 16)), dim3(256), 0, s, X, means, (int)T, (int)D, expert, scores); break;   // 16 experts: the means' L2 traffic weighs more
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
