@@ -28,7 +28,8 @@ Readings fixed here because the paper is silent, garbled or at odds with itself:
 import numpy as np
 from .bf16 import bits_to_f32, bits_to_f64, f64_to_bits
 from .sparse24 import prune24_compress, prune24_dense, HARD
-from .vnm import sqrelu
+from .vnm import sqrelu, vnm_decompress, dsqrelu_vnm
+from .gemm import vnm_spmm, vnm_wgrad, dense_nt
 
 
 def route_scores(x_bits, means_bits):
@@ -120,3 +121,45 @@ def moe_to_venom(x_bits, w1_bits, b1, means_bits, M, mode=HARD, V=64):
     y1c = expert_matmul(x_bits, perm, seg, w1_bits, b1, M, mode)
     vals, meta, colidx = venom_from_compact(y1c, perm, seg, M, V)
     return dict(expert=expert, perm=perm, seg=seg, y1c=y1c, vals=vals, meta=meta, colidx=colidx)
+
+
+def scatter_compact(c_bits, seg, M, F):
+    """[rows, 4F/M] in compact-column order -> [rows, F] with every run's columns at its expert's hidden units."""
+    full = np.zeros((c_bits.shape[0], F), dtype=np.uint16)
+    for e in range(len(seg) - 1):
+        rows = slice(int(seg[e]), int(seg[e + 1]))
+        full[rows][:, cluster_rows(e, M, F)] = c_bits[rows]
+    return full
+
+
+def ffn_router_step_ref(x_bits, w1_bits, w2_bits, b1, dy_bits, means_bits, M, mode=HARD, V=64):
+    """Alg. 1 + Alg. 2 with Alg. 3 as the activation sparsifier: the forward computes only the routed expert's hidden
+    units, and every later contraction sees the resulting V:N:M matrix (in permuted row order, padding rows zero).
+    The backward is Alg. 2 on that matrix: dy2 = dY @ sparsify24(W2.T) (needed only at the kept slots), eq. (6) on
+    y2's mask, dX with the dense W1, both weight gradients (rows of hidden units no token was routed to get exact
+    zeros from the empty sum).  Y3 and dX are returned in token order."""
+    r = moe_to_venom(x_bits, w1_bits, b1, means_bits, M, mode, V)
+    perm, seg = r["perm"], r["seg"]
+    T, D = np.asarray(x_bits).shape
+    F = np.asarray(w1_bits).shape[0]
+    real = perm >= 0
+    xp = np.zeros((len(perm), D), dtype=np.uint16)
+    dyp = np.zeros((len(perm), D), dtype=np.uint16)
+    xp[real], dyp[real] = np.asarray(x_bits)[perm[real]], np.asarray(dy_bits)[perm[real]]
+    y3p = vnm_spmm(r["vals"], r["meta"], r["colidx"], w2_bits, 0, V, M)                       # eq. (3), dense W2
+    w2t_s = prune24_dense(np.ascontiguousarray(np.asarray(w2_bits).T), mode)                   # sparsify24(W2.T), 2:4 along d_model
+    dy2 = dense_nt(dyp, w2t_s)                                                                 # eq. (4) [rows, F]
+    y1_full = scatter_compact(r["y1c"], seg, M, F)
+    dvals = dsqrelu_vnm(dy2, y1_full, r["meta"], r["colidx"], V, M)                            # eq. (6) on y2's mask
+    dxp = vnm_spmm(dvals, r["meta"], r["colidx"], w1_bits, 1, V, M)                            # eq. (7), dense W1
+    dW2 = vnm_wgrad(r["vals"], r["meta"], r["colidx"], dyp, 0, V, M)                           # eq. (5)
+    dW1 = vnm_wgrad(dvals, r["meta"], r["colidx"], xp, 1, V, M)                                # eq. (8)
+    row_of_token = np.empty(T, dtype=np.int64)
+    row_of_token[perm[real]] = np.nonzero(real)[0]
+    dy2c = np.zeros_like(r["y1c"])
+    for e in range(len(seg) - 1):
+        rows = slice(int(seg[e]), int(seg[e + 1]))
+        dy2c[rows] = dy2[rows][:, cluster_rows(e, M, F)]
+    r.update(row_of_token=row_of_token, y3p=y3p, dy2c=dy2c, dvals=dvals, dxp=dxp,
+             y3=y3p[row_of_token], dX=dxp[row_of_token], dW1=dW1, dW2=dW2)
+    return r

@@ -147,3 +147,50 @@ def test_router_output_is_what_section_2_3_would_select():
     # and the activation GEMM on it is the dense product with the masked matrix
     y3 = oracle.vnm_spmm(r["vals"], r["meta"], r["colidx"], inp["W2"], 0, 64, M)
     assert np.array_equal(y3, oracle.dense_nt(dense, inp["W2"]))
+
+
+def test_router_step_backward_is_the_gradient_of_its_forward():
+    """With W1 and W2.T already 2:4 along d_model and the routing and 2:4 masks frozen, the router step's backward is the
+    exact gradient of <dY, y3> of a forward in which every token only sees its expert's hidden units; central
+    differences in float64 on sampled entries.  Hidden units of experts that got no token have zero weight gradients."""
+    rng = np.random.default_rng(21)
+    T, D, F, M = 96, 16, 64, 16
+    inp = make_router_inputs(T, D, F, M, seed=9, zero_fraction=0.5)
+    X, dY = inp["X"], inp["dY"]
+    W1 = oracle.prune24_dense(bf(rng.standard_normal((F, D)) * 0.3))
+    W2 = np.ascontiguousarray(oracle.prune24_dense(bf(rng.standard_normal((F, D)) * 0.3)).T)
+    b1 = (rng.standard_normal(F) * 0.1).astype(np.float32)
+    means = inp["means"].copy()
+    means[3] = bf(-oracle.bits_to_f32(means[0]))                 # expert 3 mirrors expert 0: few tokens prefer it; fine either way
+    ref = oracle.ffn_router_step_ref(X, W1, W2, b1, dY, means, M)
+    ones = np.full_like(ref["vals"], 0x3F80)
+    maskp = (oracle.vnm_decompress(ones, ref["meta"], ref["colidx"], 64, M) != 0)
+    mask = maskp[ref["row_of_token"]].astype(np.float64)          # token order [T, F]
+    Xf, W1f, W2f, dYf = (oracle.bits_to_f64(a) for a in (X, W1, W2, dY))
+    b = b1.astype(np.float64)
+
+    def loss(Xa, W1a, W2a):
+        y1 = Xa @ W1a.T + b[None, :]
+        y2 = mask * np.maximum(y1, 0.0) ** 2
+        return float(((y2 @ W2a.T) * dYf).sum())
+
+    for which, key in (("X", "dX"), ("W1", "dW1"), ("W2", "dW2")):
+        got = oracle.bits_to_f64(ref[key])
+        scale = np.abs(got).max()
+        for _ in range(60):
+            args = dict(X=Xf.copy(), W1=W1f.copy(), W2=W2f.copy())
+            ij = tuple(rng.integers(0, n) for n in got.shape)
+            h = 1e-5
+            args[which][ij] += h
+            lp = loss(args["X"], args["W1"], args["W2"])
+            args[which][ij] -= 2 * h
+            lm = loss(args["X"], args["W1"], args["W2"])
+            assert abs(got[ij] - (lp - lm) / (2 * h)) <= 0.03 * scale, (key, ij)
+    # forward value, token order
+    y3 = oracle.bits_to_f64(ref["y3"])
+    y1 = oracle.bits_to_f64(oracle.f64_to_bits(Xf @ W1f.T + b[None, :]))
+    y2 = mask * oracle.bits_to_f64(oracle.sqrelu(oracle.f64_to_bits(y1)))
+    assert np.abs(y3 - y2 @ W2f.T).max() <= 0.02 * np.abs(y3).max()
+    unused = [e for e in range(M // 4) if ref["seg"][e + 1] == ref["seg"][e]]
+    for e in unused:
+        assert not ref["dW1"][oracle.cluster_rows(e, M, F)].any() and not ref["dW2"][:, oracle.cluster_rows(e, M, F)].any()
