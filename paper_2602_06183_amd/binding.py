@@ -27,6 +27,10 @@ class _Layout(ctypes.Structure):
                                                "colidx", "dy2", "dy1_vals", "y1_kept", "total")]
 
 
+class _RouterLayout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_size_t) for n in ("y1c", "vals", "meta", "colidx", "dy2c", "dvals", "total")]
+
+
 def lib_path():
     return os.path.join(_HERE, "libsparseffn.so")
 
@@ -71,6 +75,10 @@ def load():
     lib.sffn_venom_matmul_workspace_bytes.restype = sz
     lib.sffn_venom_matmul_workspace_bytes.argtypes = [i64, i64, i64, i32]
     lib.venom_expert_matmul.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(ctypes.c_int64)] + [p] * 8 + [p, sz, p]
+    lib.sffn_router_workspace_bytes.restype = sz
+    lib.sffn_router_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg)]
+    lib.sffn_router_workspace_layout.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_RouterLayout)]
+    lib.ffn_router_step.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(ctypes.c_int64)] + [p] * 11 + [p, sz, p]
     lib.sffn_profile_enable.argtypes = [i32]
     lib.sffn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_char_p), i32]
     _LIB = lib
@@ -342,3 +350,41 @@ def moe_to_venom(X, W1, b1, means, M, mode=MODE_HARD):
     vals, meta, colidx, y1c = venom_expert_matmul(X, r["perm"], r["seg"], W1, b1, M, mode)
     r.update(vals=vals, meta=meta, colidx=colidx, y1c=y1c)
     return r
+
+
+class FfnRouterStep:
+    """ffn_router_step with a workspace allocated once (shapes and the routing's row capacity are fixed by T, D, F, M)."""
+
+    def __init__(self, T, D, F, M, mode=MODE_HARD, device="cuda"):
+        self.T, self.D, self.F, self.M, self.mode = T, D, F, M, mode
+        self.cfg = _cfg(T, D, F, mode, M=M)
+        lay = _RouterLayout()
+        _check(load().sffn_router_workspace_layout(ctypes.byref(self.cfg), ctypes.byref(lay)))
+        self.layout = {n: getattr(lay, n) for n, _ in _RouterLayout._fields_}
+        self.rows = load().sffn_venom_rows(T, M)
+        self.ws = _u8((self.layout["total"],), device)
+        self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
+        self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
+
+    def __call__(self, route, X, W1, W2, b1, dY):
+        """route: the dict venom_route returned for X."""
+        E = self.M // 4
+        seg_arr = (ctypes.c_int64 * (E + 1))(*[int(v) for v in route["seg"]])
+        _check(load().ffn_router_step(ctypes.byref(self.cfg), seg_arr, _ptr(route["perm"]), _ptr(route["row_of_token"]), _ptr(X), _ptr(W1),
+                                      _ptr(W2), _ptr(b1), _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2),
+                                      _ptr(self.ws), self.layout["total"], _stream()))
+        return self.Y3, self.dX, self.dW1, self.dW2
+
+    def saved(self):
+        rows, Kc, L = self.rows, 4 * self.F // self.M, self.layout
+
+        def view(off, shape, dtype):
+            n = 1
+            for d in shape:
+                n *= d
+            nbytes = n * (2 if dtype == torch.bfloat16 else 1)
+            return self.ws[off:off + nbytes].view(dtype).view(shape)
+
+        return dict(y1c=view(L["y1c"], (rows, Kc), torch.bfloat16), vals=view(L["vals"], (rows, Kc // 2), torch.bfloat16),
+                    meta=view(L["meta"], (rows, Kc // 8), torch.uint8), colidx=view(L["colidx"], (rows // 64, self.F // self.M, 4), torch.uint8),
+                    dy2c=view(L["dy2c"], (rows, Kc), torch.bfloat16), dvals=view(L["dvals"], (rows, Kc // 2), torch.bfloat16))

@@ -63,7 +63,18 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     const int Kld = K;                   // K extent of the stored operands (block-row stride)
     const int tok_ld = grp.n ? grp.seg[grp.n] : Rb;       // tokens in the token-indexed outputs of the V:N:M epilogue
     int i_base = 0, j_base = 0;
-    if (grp.n) {
+    int expert_id = 0;
+    if (!SPARSE && !BLOCKED && grp.n && grp.role == 2) {
+        // every expert has its own tiles_m x tiles_n output and contracts over its own k range of the shared operands
+        const int per = tiles_m * tiles_n;
+        expert_id = L / per;
+        L -= expert_id * per;
+        if (expert_id >= grp.n) return;
+        const int k0 = grp.seg[expert_id];
+        K = grp.seg[expert_id + 1] - k0;
+        a_vals += k0; B += k0;
+        out += expert_id * grp.out_stride;
+    } else if (grp.n) {
         int e = 0;
         {
             const int other = grp.role == 0 ? tiles_n : tiles_m;
@@ -339,8 +350,16 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                 for (int p = 0; p < WN / 8; ++p) {
                     const int row = p * 8 + (lane >> 3), ch = lane & 7;
                     const int j = t0 + row, i = f0 + ch * 8;
-                    if (j < Rb && i < Ra)
-                        *reinterpret_cast<uint4*>(out + (int64_t)j * ldo + i) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
+                    if (j < Rb && i < Ra) {
+                        const uint4 w = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
+                        if (EPI == 0 && grp.map_logM) {     // 8 consecutive compact columns = two groups of four hidden units, M apart
+                            uint16_t* o = out + (int64_t)j * ldo + ((int64_t)(i >> 2) << grp.map_logM) + 4 * expert_id;
+                            *reinterpret_cast<uint2*>(o) = make_uint2(w.x, w.y);
+                            *reinterpret_cast<uint2*>(o + ((int64_t)1 << grp.map_logM)) = make_uint2(w.z, w.w);
+                        } else {
+                            *reinterpret_cast<uint4*>(out + (int64_t)j * ldo + i) = w;
+                        }
+                    }
                 }
             }
             if (EPI == 3) {
@@ -483,8 +502,10 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
             for (int p = 0; p < 32 * CH / 64; ++p) {
                 const int e = lane + 64 * p, row = e / CH, ch = e % CH;
                 const int i = i0 + wm * WM + a * 32 + row, j = j0 + wn * WN + ch * 8;
-                if (i < Ra && j < Rb)
-                    *reinterpret_cast<uint4*>(out + (int64_t)i * ldo + j) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
+                if (i < Ra && j < Rb) {
+                    const int64_t io = grp.map_logM ? ((int64_t)(i >> 2) << grp.map_logM) + 4 * expert_id + (i & 3) : i;
+                    *reinterpret_cast<uint4*>(out + io * ldo + j) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
+                }
             }
             __syncthreads();
         }
@@ -494,6 +515,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
 // Grid of a launch: one workgroup per 256 x 256 output tile; grouped: per expert, over its token segment.
 static unsigned grid_tiles(int tiles_m, int tiles_n, const GemmGroup& g) {
     if (g.n == 0) return (unsigned)(tiles_m * tiles_n);
+    if (g.role == 2) return (unsigned)(g.n * tiles_m * tiles_n);
     int tok_tiles = 0;
     for (int e = 0; e < g.n; ++e) tok_tiles += (g.seg[e + 1] - g.seg[e] + 255) / 256;
     return (unsigned)(tok_tiles * (g.role == 0 ? tiles_n : tiles_m));
@@ -505,7 +527,8 @@ static hipError_t launch_v2(const uint16_t* a_vals, const uint8_t* a_meta, const
                             const GemmGroup* grp) {
     const int tiles_m = (int)((Ra + 255) / 256), tiles_n = (int)((Rb + 255) / 256);
     const GemmGroup g = grp ? *grp : GemmGroup();
-    if (g.n && (!blocked || g.n > GemmGroup::kMaxExperts || g.role == 2)) return hipErrorInvalidValue;
+    if (g.n > GemmGroup::kMaxExperts) return hipErrorInvalidValue;
+    if (g.n && g.role == 2 ? (SPARSE || blocked) : (g.n && !blocked)) return hipErrorInvalidValue;   // role 2: dense row-major only; roles 0, 1: blocked only
     const unsigned tiles = grid_tiles(tiles_m, tiles_n, g);
     if (tiles == 0) return hipSuccess;
     dim3 grid(tiles);
@@ -522,9 +545,10 @@ static hipError_t launch_v2(const uint16_t* a_vals, const uint8_t* a_meta, const
 }
 
 hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
-                             int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
-    if (sparse_a) return launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s, nullptr);
-    return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s, nullptr);
+                             int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s,
+                             const GemmGroup* grp) {
+    if (sparse_a) return grp ? hipErrorInvalidValue : launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s, nullptr);
+    return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s, grp);
 }
 
 hipError_t launch_spmm_blocked(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t Ra, int64_t Rb,

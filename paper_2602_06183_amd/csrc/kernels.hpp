@@ -43,6 +43,9 @@ struct GemmGroup {
     int n = 0;                      // 0: ordinary single contraction
     int role = 0;
     int64_t a_stride = 0, m_stride = 0, b_stride = 0, bias_stride = 0, out_stride = 0;
+    // role 2 on row-major operands (weight gradients of the neuron-level experts, Section 3.3): output index i of expert e is
+    // compact column i of its hidden units and lands at hidden unit (i / 4) * M + 4 e + i % 4 of the one shared output (0: off)
+    int map_logM = 0;
     int32_t seg[kMaxExperts + 1] = {0};
 };
 
@@ -95,7 +98,8 @@ hipError_t launch_gemm_vnm_epilogue(const uint16_t* a_vals, const uint8_t* a_met
 hipError_t launch_spmm_blocked(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t Ra, int64_t Rb,
                                int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias,
-                          int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
+                          int64_t Ra, int64_t Rb, int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s,
+                          const GemmGroup* grp = nullptr);   // grp: dense A only, role 2 (every expert contracts over its own k range)
 
 // eqs. (5), (8): C[f, n] = sum_t A[t, f] * G[t, n] with A given as `atc` (compacted transposed activation written by the
 // V:N:M epilogue) + kmask (kept-column bit masks, [T / 64, F / 8]), G = [N rows, T] in the blocked layout; out_i_contig: out[n * ldo + f], else out[f * ldo + n].
@@ -105,7 +109,11 @@ hipError_t launch_venom_route(const uint16_t* X, const uint16_t* means, int64_t 
                               hipStream_t s);
 hipError_t launch_venom_permute(const int32_t* expert, int64_t T, int E, int64_t cap, int32_t* blockcnt, int32_t* seg, int32_t* perm,
                                 int32_t* row_of_token, hipStream_t s);
-hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, hipStream_t s);
+hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, int blocked, hipStream_t s);
+hipError_t launch_venom_unpermute(const uint16_t* src, const int32_t* row_of_token, int64_t T, int64_t D, uint16_t* out, hipStream_t s);
+hipError_t launch_venom_dsqrelu_compact(const uint16_t* dy2c, const uint16_t* y1c, const uint8_t* meta, int64_t rows, int64_t Kc,
+                                        uint16_t* dvals, hipStream_t s);
+hipError_t launch_venom_expand_t_compact(const uint16_t* vals, const uint8_t* meta, int64_t rows, int64_t Kc, uint16_t* at, hipStream_t s);
 hipError_t launch_fill_bytes(void* p, uint8_t v, size_t n_bytes, hipStream_t s);
 hipError_t launch_venom_colidx(const GemmGroup& g, int64_t cap, int64_t groups, uint8_t* colidx, hipStream_t s);
 

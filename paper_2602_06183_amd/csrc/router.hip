@@ -133,9 +133,9 @@ __global__ void __launch_bounds__(256) venom_scatter_kernel(const int32_t* __res
     }
 }
 
-// X rows in permuted order (zero rows for padding), blocked operand layout: one thread per 16 bytes.
+// X rows in permuted order (zero rows for padding), blocked operand layout or row-major: one thread per 16 bytes.
 __global__ void __launch_bounds__(256) venom_gather_x_kernel(const uint16_t* __restrict__ X, const int32_t* __restrict__ perm, int cap, int D,
-                                                            uint16_t* __restrict__ xb) {
+                                                            uint16_t* __restrict__ xb, int blocked) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int cpr = D >> 3;
     const int64_t r = idx / cpr;
@@ -144,7 +144,78 @@ __global__ void __launch_bounds__(256) venom_gather_x_kernel(const uint16_t* __r
     const int t = perm[r];
     uint4 v = make_uint4(0, 0, 0, 0);
     if (t >= 0) v = *reinterpret_cast<const uint4*>(X + (int64_t)t * D + c * 8);
-    *reinterpret_cast<uint4*>(xb + blk_off(r, c * 8, D >> 5)) = v;
+    *reinterpret_cast<uint4*>(xb + (blocked ? blk_off(r, c * 8, D >> 5) : r * D + c * 8)) = v;
+}
+
+// out[t, :] = src[row_of_token[t], :]: results of the permuted row order back in token order.
+__global__ void __launch_bounds__(256) venom_unpermute_kernel(const uint16_t* __restrict__ src, const int32_t* __restrict__ row_of_token, int T, int D,
+                                                             uint16_t* __restrict__ out) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int cpr = D >> 3;
+    const int64_t t = idx / cpr;
+    const int c = (int)(idx - t * cpr);
+    if (t >= T) return;
+    *reinterpret_cast<uint4*>(out + t * D + c * 8) = *reinterpret_cast<const uint4*>(src + (int64_t)row_of_token[t] * D + c * 8);
+}
+
+// eq. (6) on the compact arrays of the router's output: slot s of group g of row r sits at compact column 4 g + p_s
+// (p_s from the metadata nibble); dvals = bf16(2 * dy2c * max(y1c, 0)) there.  One thread per metadata byte (two groups).
+__global__ void __launch_bounds__(256) venom_dsqrelu_compact_kernel(const uint16_t* __restrict__ dy2c, const uint16_t* __restrict__ y1c,
+                                                                   const uint8_t* __restrict__ meta, int64_t n_bytes,
+                                                                   uint16_t* __restrict__ dvals) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n_bytes) return;
+    const uint4 dv = *reinterpret_cast<const uint4*>(dy2c + idx * 8);
+    const uint4 yv = *reinterpret_cast<const uint4*>(y1c + idx * 8);
+    const uint32_t mb = meta[idx];
+    const uint32_t dw[4] = {dv.x, dv.y, dv.z, dv.w}, yw[4] = {yv.x, yv.y, yv.z, yv.w};
+    uint32_t o[2];
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+        const uint32_t nib = (mb >> (4 * g)) & 0xFu;
+        uint32_t r[2];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const uint32_t p = (nib >> (2 * s)) & 3u;                       // position inside the group of four
+            const uint32_t d16 = (dw[2 * g + (p >> 1)] >> (16 * (p & 1))) & 0xFFFFu;
+            const uint32_t y16 = (yw[2 * g + (p >> 1)] >> (16 * (p & 1))) & 0xFFFFu;
+            const float y = bf2f(y16);
+            r[s] = f2bf(2.0f * bf2f(d16) * (y > 0.0f ? y : 0.0f));
+        }
+        o[g] = r[0] | (r[1] << 16);
+    }
+    *reinterpret_cast<uint2*>(dvals + idx * 4) = make_uint2(o[0], o[1]);
+}
+
+// (vals [rows, Kc / 2], meta [rows, Kc / 8]) -> the dense transposed matrix at[j, r] ([Kc, rows], row-major), zeros at the
+// dropped positions: the A operand of the weight-gradient contractions over each expert's run.  64 x 64 tiles through LDS.
+__global__ void __launch_bounds__(256) venom_expand_t_compact_kernel(const uint16_t* __restrict__ vals, const uint8_t* __restrict__ meta,
+                                                                    int64_t rows, int Kc, uint16_t* __restrict__ at) {
+    __shared__ uint16_t tile[64][64 + 2];           // [compact column][row]
+    const int tid = threadIdx.x;
+    const int64_t r0 = (int64_t)blockIdx.y * 64;
+    const int j0 = blockIdx.x * 64;
+    // 64 rows x 16 groups: thread -> (row = tid / 4 [+ 0], groups 4 (tid % 4) .. + 3)
+    {
+        const int rr = tid >> 2, g4 = (tid & 3) * 4;
+        const uint4 v = *reinterpret_cast<const uint4*>(vals + (r0 + rr) * (Kc / 2) + (j0 / 2) + g4 * 2);      // 4 groups x 2 survivors
+        const uint32_t mb = *reinterpret_cast<const uint16_t*>(meta + (r0 + rr) * (Kc / 8) + (j0 / 8) + g4 / 2);  // 4 nibbles
+        const uint32_t vw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const uint32_t nib = (mb >> (4 * g)) & 0xFu, p0 = nib & 3u, p1 = nib >> 2;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                tile[(g4 + g) * 4 + c][rr] = (uint16_t)((c == (int)p0) ? (vw[g] & 0xFFFFu) : (c == (int)p1) ? (vw[g] >> 16) : 0u);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int e = tid + 256 * i, jj = e >> 3, seg8 = (e & 7) * 8;
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(&tile[jj][seg8]);
+        *reinterpret_cast<uint4*>(at + (int64_t)(j0 + jj) * rows + r0 + seg8) = make_uint4(p[0], p[1], p[2], p[3]);
+    }
 }
 
 // colidx[tb, g, :] = (4e, 4e + 1, 4e + 2, 4e + 3) for the 64-row blocks of expert e's run; blocks past the last run: e = 0.
@@ -196,9 +267,28 @@ hipError_t launch_venom_permute(const int32_t* expert, int64_t T, int E, int64_t
     return hipGetLastError();
 }
 
-hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, hipStream_t s) {
+hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, int blocked, hipStream_t s) {
     const int64_t n = cap * (D / 8);
-    hipLaunchKernelGGL(venom_gather_x_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, X, perm, (int)cap, (int)D, xb);
+    hipLaunchKernelGGL(venom_gather_x_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, X, perm, (int)cap, (int)D, xb, blocked);
+    return hipGetLastError();
+}
+
+hipError_t launch_venom_unpermute(const uint16_t* src, const int32_t* row_of_token, int64_t T, int64_t D, uint16_t* out, hipStream_t s) {
+    const int64_t n = T * (D / 8);
+    hipLaunchKernelGGL(venom_unpermute_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, row_of_token, (int)T, (int)D, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_venom_dsqrelu_compact(const uint16_t* dy2c, const uint16_t* y1c, const uint8_t* meta, int64_t rows, int64_t Kc,
+                                        uint16_t* dvals, hipStream_t s) {
+    const int64_t n = rows * (Kc / 8);
+    hipLaunchKernelGGL(venom_dsqrelu_compact_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dy2c, y1c, meta, n, dvals);
+    return hipGetLastError();
+}
+
+hipError_t launch_venom_expand_t_compact(const uint16_t* vals, const uint8_t* meta, int64_t rows, int64_t Kc, uint16_t* at, hipStream_t s) {
+    dim3 grid((unsigned)(Kc / 64), (unsigned)(rows / 64));
+    hipLaunchKernelGGL(venom_expand_t_compact_kernel, grid, dim3(256), 0, s, vals, meta, rows, (int)Kc, at);
     return hipGetLastError();
 }
 

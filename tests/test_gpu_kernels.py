@@ -469,3 +469,44 @@ def test_moe_to_venom_with_empty_experts():
     ov, om, oc = oracle.venom_from_compact(y1c, perm, seg, M)
     assert np.array_equal(to_bits(r["colidx"]), oc) and np.array_equal(to_bits(r["meta"]), om) and np.array_equal(to_bits(r["vals"]), ov)
     assert not to_bits(r["vals"])[T:].any()
+
+
+@pytest.mark.parametrize("M,mode,T,D,F", [(8, sffn.MODE_HARD, 700, 128, 512), (16, sffn.MODE_SOFT, 1000, 192, 1024),
+                                          (32, sffn.MODE_HARD, 333, 64, 2048), (64, sffn.MODE_HARD, 2000, 256, 1024)])
+def test_ffn_router_step_against_oracle(M, mode, T, D, F):
+    """The router's whole training step, teacher-forced stage by stage: routing bit-exact; y1c, dy2c and the four
+    outputs within the GEMM tolerance of the oracle's contraction on the GPU's own packed operands; packing and
+    eq. (6) bit-exact from the GPU's y1c / dy2c."""
+    inp = make_router_inputs(T, D, F, M, seed=3 * M + T, zero_fraction=0.75)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    route = sffn.venom_route(dev["X"], dev["means"], M)
+    step = sffn.FfnRouterStep(T, D, F, M, mode)
+    outs = step(route, dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    torch.cuda.synchronize()
+    Y3, dX, dW1, dW2 = (to_bits(t) for t in outs)
+    sv = {k: to_bits(v) for k, v in step.saved().items()}
+    expert = oracle.route_top1(oracle.route_scores(inp["X"], inp["means"]))
+    perm, seg = oracle.expert_permutation(expert, M // 4)
+    assert np.array_equal(to_bits(route["perm"]), perm) and route["seg"] == [int(v) for v in seg]
+    rot = to_bits(route["row_of_token"]).astype(np.int64)
+    real = perm >= 0
+    xp, dyp = np.zeros((len(perm), D), dtype=np.uint16), np.zeros((len(perm), D), dtype=np.uint16)
+    xp[real], dyp[real] = inp["X"][perm[real]], inp["dY"][perm[real]]
+    # forward
+    assert_gemm_close(sv["y1c"], oracle.expert_matmul(inp["X"], perm, seg, inp["W1"], inp["b1"], M, mode), "y1c")
+    ov, om, oc = oracle.venom_from_compact(sv["y1c"], perm, seg, M)
+    assert np.array_equal(sv["colidx"], oc) and np.array_equal(sv["meta"], om) and np.array_equal(sv["vals"], ov)
+    assert_gemm_close(Y3, oracle.vnm_spmm(ov, om, oc, inp["W2"], 0, 64, M)[rot], "y3")
+    # backward
+    w2t_s = oracle.prune24_dense(np.ascontiguousarray(inp["W2"].T), mode)
+    dy2 = oracle.dense_nt(dyp, w2t_s)
+    dy2c_ref = np.zeros_like(sv["dy2c"])
+    for e in range(M // 4):
+        rows = slice(int(seg[e]), int(seg[e + 1]))
+        dy2c_ref[rows] = dy2[rows][:, oracle.cluster_rows(e, M, F)]
+    assert_gemm_close(sv["dy2c"], dy2c_ref, "dy2c")
+    dv = oracle.dsqrelu_vnm(oracle.scatter_compact(sv["dy2c"], seg, M, F), oracle.scatter_compact(sv["y1c"], seg, M, F), om, oc, 64, M)
+    assert np.array_equal(sv["dvals"], dv)
+    assert_gemm_close(dX, oracle.vnm_spmm(dv, om, oc, inp["W1"], 1, 64, M)[rot], "dX")
+    assert_gemm_close(dW2, oracle.vnm_wgrad(ov, om, oc, dyp, 0, 64, M), "dW2")
+    assert_gemm_close(dW1, oracle.vnm_wgrad(dv, om, oc, xp, 1, 64, M), "dW1")
