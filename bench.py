@@ -23,13 +23,17 @@ def algorithmic_flops(stage, T, D, F, M=8):
     """Multiply-adds the method itself needs (non-zero products), times two, per launch."""
     tdf = float(T) * D * F
     act = 4.0 / M * tdf                                          # V:2:M activations: 2 of M survive (M = 8: a quarter)
+    if stage.startswith("router/"):                              # neuron-level experts: every contraction covers 4 / M of the hidden units
+        return act if stage in ("router/y1c+sqrelu+2:4", "router/dy2c", "router/y3", "router/dX", "router/dW2", "router/dW1") else None
     return {"step/y1+sqrelu_vnm_compress": tdf, "step/dy2+dsqrelu_vnm": tdf, "step/y1": tdf, "step/dy2": tdf,   # 2:4 weights: half of K survives
             "step/y3": act, "step/dX": act, "step/dW2": act, "step/dW1": act}.get(stage)
 
 
-def executed_flops(stage, T, D, F):
+def executed_flops(stage, T, D, F, M=8):
     """Flops the matrix cores are issued for (dense-equivalent of the instructions used)."""
     tdf = float(T) * D * F
+    if stage.startswith("router/"):
+        return 8.0 / M * tdf if stage in ("router/y1c+sqrelu+2:4", "router/dy2c", "router/y3", "router/dX", "router/dW2", "router/dW1") else None
     return {"step/y1+sqrelu_vnm_compress": 2 * tdf, "step/dy2+dsqrelu_vnm": 2 * tdf, "step/y1": 2 * tdf, "step/dy2": 2 * tdf,
             "step/y3": 2 * tdf, "step/dX": 2 * tdf, "step/dW2": 2 * tdf, "step/dW1": 2 * tdf}.get(stage)
 
@@ -37,7 +41,10 @@ def executed_flops(stage, T, D, F):
 KERNEL_OF_STAGE = {"step/y1+sqrelu_vnm_compress": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dy2+dsqrelu_vnm": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
                    "step/y1": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dy2": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
                    "step/y3": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dX": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
-                   "step/dW2": "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>", "step/dW1": "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>"}
+                   "step/dW2": "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>", "step/dW1": "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>",
+                   "router/y1c+sqrelu+2:4": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "router/dy2c": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
+                   "router/y3": "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>", "router/dX": "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>",
+                   "router/dW2": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>", "router/dW1": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>"}
 
 
 def main():
@@ -50,6 +57,8 @@ def main():
     ap.add_argument("--mode", default="hard", choices=["hard", "soft"])
     ap.add_argument("--M", type=int, default=8, choices=[8, 16, 32, 64],
                     help="V:2:M block width of the activation format (Table 5); 8 is the headline configuration, wider blocks run the unfused path")
+    ap.add_argument("--router", action="store_true",
+                    help="time the neuron-level router's training step (Section 3.3: venom_route + ffn_router_step, M / 4 experts) instead of the magnitude-based V:N:M step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference kernel for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -68,6 +77,8 @@ def main():
     M = args.M
     if moe and M != 8:
         sys.exit("bench.py: the grouped step is built for M = 8 only")
+    if moe and args.router:
+        sys.exit("bench.py: --router runs on the single-FFN workloads")
     if moe:
         _, D, F = CONFIGS["moe_expert"]
         inp = make_moe_inputs(16384, 8, 2, D, F, seed=0, zero_fraction=args.zero_fraction)
@@ -77,13 +88,21 @@ def main():
         T, D, F = CONFIGS[args.workload]
         inp = make_ffn_inputs(T, D, F, seed=0, zero_fraction=args.zero_fraction)
 
+    def sffn_bits(t):            # device bf16 tensor -> numpy bit patterns (for the CPU oracle leg)
+        return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
     def dev(a):
         if a.dtype == np.uint16:
             return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
         return torch.from_numpy(a).cuda()
 
     X, W1, W2, b1, dY = (dev(inp[k]) for k in ("X", "W1", "W2", "b1", "dY"))
-    step = sffn.FfnStepGrouped(seg, D, F, mode) if moe else sffn.FfnStep(T, D, F, mode, M=M)
+    if args.router:
+        from workload import make_router_inputs
+        means = dev(make_router_inputs(64, D, 4 * M, M, seed=0)["means"])
+        step = sffn.FfnRouterStep(T, D, F, M, mode)
+    else:
+        step = sffn.FfnStepGrouped(seg, D, F, mode) if moe else sffn.FfnStep(T, D, F, mode, M=M)
     flops = 12.0 * T * D * F
 
     # ---- dense bf16 FFN step on hipBLASLt (torch.matmul), same shapes, same process -------------
@@ -118,8 +137,12 @@ def main():
         def dense_step():
             dense_ffn(X, W1, W2, b1h, dY, y1, y2, y3, dy2, dy1, dXd, dW1d, dW2d)
 
-    def sparse_step():
-        step(X, W1, W2, b1, dY)
+    if args.router:
+        def sparse_step():          # Alg. 3 steps 1-2 (with the read-back of the run offsets), then the grouped step
+            step(sffn.venom_route(X, means, M), X, W1, W2, b1, dY)
+    else:
+        def sparse_step():
+            step(X, W1, W2, b1, dY)
 
     def timed(fn, n):
         torch.cuda.synchronize()
@@ -164,7 +187,7 @@ def main():
     launches = by_kernel[dom_kernel]
     avg_ms = sum(ms for _, ms in launches) / len(launches)
     alg = sum(algorithmic_flops(n, T, D, F, M) or 0.0 for n, _ in launches) / len(launches)
-    exe = sum(executed_flops(n, T, D, F) or 0.0 for n, _ in launches) / len(launches)
+    exe = sum(executed_flops(n, T, D, F, M) or 0.0 for n, _ in launches) / len(launches)
     achieved = alg / (avg_ms * 1e-3) / 1e12
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
@@ -247,7 +270,9 @@ def main():
     # ---- how much of the activation's L1 mass the V:N:M format keeps (sum of kept y2 / sum of all y2): one extra,
     #      untimed step that also stores the dense y1; plain torch reductions, measurement only ------------------
     retained = None
-    if not moe:
+    if args.router:
+        zero_frac = None
+    elif not moe:
         del y2, dy2, dy1                                   # the dense baseline's buffers are no longer needed
         chk = sffn.FfnStep(T, D, F, mode, keep_dense=True, M=M)
         chk(X, W1, W2, b1, dY)
@@ -271,11 +296,14 @@ def main():
         Ts = min(T, max(64, (int(3.0e11 / (12.0 * D * F)) // 64) * 64))      # about 0.3 TFLOP of fp64 matmul
         w1o, w2o, b1o = (inp[k][0] if moe else inp[k] for k in ("W1", "W2", "b1"))    # moe: expert 0 on its first tokens
         t0 = time.perf_counter()
-        oracle.ffn_sparse_step_ref(inp["X"][:Ts], w1o, w2o, b1o, inp["dY"][:Ts], mode)
+        if args.router:
+            oracle.ffn_router_step_ref(inp["X"][:Ts], w1o, w2o, b1o, inp["dY"][:Ts], sffn_bits(means), M, mode)
+        else:
+            oracle.ffn_sparse_step_ref(inp["X"][:Ts], w1o, w2o, b1o, inp["dY"][:Ts], mode, 64, M)
         dt = time.perf_counter() - t0
         cpu = {"value": round(12.0 * Ts * D * F / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-               "sample": "oracle.ffn_sparse_step_ref on the first %d of %d tokens (same D, F, weights%s), %.1f s"
-                         % (Ts, T, " of expert 0" if moe else "", dt)}
+               "sample": "oracle.%s on the first %d of %d tokens (same D, F, weights%s), %.1f s"
+                         % ("ffn_router_step_ref" if args.router else "ffn_sparse_step_ref", Ts, T, " of expert 0" if moe else "", dt)}
 
     value = flops / (ms_sparse * 1e-3) / 1e12
     out = {
@@ -286,8 +314,10 @@ def main():
         "config": {"workload": ("moe: 8 experts, 16384 tokens routed top-2 = %d token slots in segments %s (64-row aligned), d_model=%d, d_ff=%d per expert, "
                                 "2:4 weights (%s), V:N:M 64:2:8 SquaredReLU, zero fraction %.2f, seed 0; one grouped launch per stage"
                                 % (T, seg, D, F, args.mode, args.zero_fraction)) if moe else
-                               "%s: one FFN layer, T=%d tokens, d_model=%d, d_ff=%d, 2:4 weights (%s), V:N:M 64:2:%d SquaredReLU, zero fraction %.2f, seed 0"
-                               % (args.workload, T, D, F, args.mode, M, args.zero_fraction)},
+                               "%s: one FFN layer, T=%d tokens, d_model=%d, d_ff=%d, 2:4 weights (%s), V:N:M 64:2:%d SquaredReLU%s, zero fraction %.2f, seed 0"
+                               % (args.workload, T, D, F, args.mode, M,
+                                  " produced by the neuron-level router (%d experts, routing + grouping inside the timed step)" % (M // 4) if args.router else "",
+                                  args.zero_fraction)},
         "frac_of_mfma_peak": round(value / MFMA_BF16_PEAK_TFLOPS, 4),
         "dense_ms_per_step": round(ms_dense, 4), "dense_tflops": round(flops / (ms_dense * 1e-3) / 1e12, 2),
         "dense_frac_of_mfma_peak": round(flops / (ms_dense * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
