@@ -324,7 +324,7 @@ int venom_expert_matmul(const sffn_cfg* cfg, const int64_t* seg_offsets, const u
 namespace {
 struct RouterLayout {
     sffn_router_layout pub;
-    size_t xp, xpt, xb, dyp, dypt, dyb, w1cv, w1cm, w1cvb, w1cmb, w2t, w2cv, w2cm, w2cvb, w2cmb, at, y3p, dxp, total;
+    size_t xp, xpt, xb, dyp, dypt, dyb, w1cv, w1cm, w1cvb, w1cmb, w2t, w2cv, w2cm, w2cvb, w2cmb, at, y3p, dxp, avb, amb, wcb, total;
 };
 bool make_router_layout(const sffn_cfg* c, RouterLayout* L) {
     if (!c || c->T <= 0 || !mult64(c->D) || !mult64(c->F) || !vnm_ok(c->V, c->M)) return false;
@@ -342,6 +342,8 @@ bool make_router_layout(const sffn_cfg* c, RouterLayout* L) {
     L->w2cv = take(F * D); L->w2cm = take(F * D / 8); L->w2cvb = take(F * D); L->w2cmb = take(F * D / 8);
     L->at = take(rows * Kc * 2);
     L->y3p = take(rows * D * 2); L->dxp = take(rows * D * 2);
+    L->avb = take(rows * Kc); L->amb = take(rows * Kc / 8);     // packed activation (y2, then dy1) in the blocked operand layout
+    L->wcb = take(F * D * 2);                                    // per expert: its slice of W2 (then of W1.T) as [D, Kc], blocked
     L->total = off; L->pub.total = off;
     return true;
 }
@@ -373,8 +375,6 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
     const int64_t Kc = 4 * F / M, rows = sffn_venom_rows(T, M);
     REQUIRE(rows < 65536 * 64 && fits_int(F) && fits_int(D) && fits_int(rows * (D / 8)) && fits_int(rows * (Kc / 8)), SFFN_EUNSUPPORTED,
             "ffn_router_step: dimension too large");
-    REQUIRE(vnm_spmm_gather_ok(rows, D, F, M) && F * D * 2 < ((int64_t)1 << 32), SFFN_EUNSUPPORTED,
-            "ffn_router_step: 4F/M must be at most 7168 (the gathered-row kernel's limit)");
     REQUIRE(aligned16(perm) && aligned16(row_of_token) && aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(b1) && aligned16(dY) &&
                 aligned16(Y3) && aligned16(dX) && aligned16(dW1) && aligned16(dW2) && aligned16(workspace), SFFN_EINVAL,
             "ffn_router_step: pointers must be 16-byte aligned");
@@ -386,6 +386,8 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
         REQUIRE(seg_offsets[e + 1] >= seg_offsets[e] && seg_offsets[e + 1] % 64 == 0, SFFN_EINVAL, "ffn_router_step: seg_offsets must be ascending multiples of 64");
     for (int e = 0; e <= E; ++e) g1.seg[e] = (int32_t)seg_offsets[e];
     g1.a_stride = Kc * D / 2; g1.m_stride = Kc * D / 8; g1.bias_stride = 4;
+    GemmGroup g0 = g1;                                  // eqs. (3), (7): token runs along i, the expert's [D, Kc] weight slice as B
+    g0.role = 0; g0.a_stride = g0.m_stride = g0.bias_stride = 0; g0.b_stride = D * Kc;
     GemmGroup g2 = g1;                                  // weight gradients: every expert contracts over its own run
     g2.role = 2; g2.a_stride = g2.m_stride = g2.bias_stride = 0; g2.out_stride = 0;
     const int logM = M == 8 ? 3 : M == 16 ? 4 : M == 32 ? 5 : 6;
@@ -403,6 +405,7 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
     uint16_t* w2cv = (uint16_t*)(ws + L.w2cv); uint8_t* w2cm = ws + L.w2cm; uint16_t* w2cvb = (uint16_t*)(ws + L.w2cvb); uint8_t* w2cmb = ws + L.w2cmb;
     uint16_t* at = (uint16_t*)(ws + L.at);
     uint16_t* y3p = (uint16_t*)(ws + L.y3p); uint16_t* dxp = (uint16_t*)(ws + L.dxp);
+    uint16_t* avb = (uint16_t*)(ws + L.avb); uint8_t* amb = ws + L.amb; uint16_t* wcb = (uint16_t*)(ws + L.wcb);
 
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
     // ---- Alg. 1 with Alg. 3 as the sparsifier ---------------------------------------------------------------------
@@ -418,13 +421,17 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
         LAUNCH(launch_fill_bytes(dy2c + used * Kc, 0, (size_t)tail * Kc * 2, s), "router/clear");
         LAUNCH(launch_fill_bytes(dvals + used * (Kc / 2), 0, (size_t)tail * Kc, s), "router/clear");
     }
+    // Inside a run every 64-row block keeps the same columns, so eqs. (3), (7) are plain grouped 2:4 contractions of the
+    // packed [rows, Kc] activation with the expert's own [D, Kc] slice of W2 / W1.T (256 x 256 tiles; gathering rows per
+    // 64-row block would re-read the same lines from every CU at once)
     {
         VnmEpilogue ep;
-        ep.mode = 3; ep.store_dense = 1; ep.vals = vals; ep.meta = meta; ep.perm = perm; ep.logM = logM;
+        ep.mode = 3; ep.store_dense = 1; ep.vals = vals; ep.meta = meta; ep.perm = perm; ep.logM = logM; ep.v24 = avb; ep.m24 = amb;
         STAGE(launch_gemm_vnm_epilogue(w1cvb, w1cmb, xb, b1, Kc, rows, D, y1c, ep, s, &g1), "router/y1c+sqrelu+2:4");    // eqs. (1), (2), Section 2.3
     }
     STAGE(launch_transpose(W2, D, F, F, w2t, 0, nullptr, s), "router/W2.T");
-    STAGE(launch_vnm_spmm_gather(vals, meta, colidx, w2t, D, rows, D, F, M, y3p, D, s), "router/y3");                     // eq. (3)
+    STAGE(launch_transpose(w2t, Kc, D, D, wcb, 1, nullptr, s, E, M), "router/W2[:,e]");
+    STAGE(launch_spmm_blocked(avb, amb, wcb, nullptr, rows, D, Kc, 0, y3p, D, s, &g0), "router/y3");                      // eq. (3)
     STAGE(launch_venom_unpermute(y3p, row_of_token, T, D, Y3, s), "router/unpermute(y3)");
     // ---- Alg. 2 ------------------------------------------------------------------------------------------------------
     STAGE(launch_prune24_step(w2t, F, D, D, 0, cfg->mode, w2cv, w2cm, w2cvb, w2cmb, nullptr, s, 1, M), "router/prune24(W2.T)");
@@ -438,8 +445,9 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
         const VnmEpilogue plain;
         STAGE(launch_gemm_vnm_epilogue(w2cvb, w2cmb, dyb, nullptr, Kc, rows, D, dy2c, plain, s, &g4), "router/dy2c");      // eq. (4) at the expert's columns
     }
-    if (used > 0) STAGE(launch_venom_dsqrelu_compact(dy2c, y1c, meta, used, Kc, dvals, s), "router/dsqrelu");               // eq. (6)
-    STAGE(launch_vnm_spmm_gather(dvals, meta, colidx, W1, D, rows, D, F, M, dxp, D, s), "router/dX");                     // eq. (7)
+    if (used > 0) STAGE(launch_venom_dsqrelu_compact(dy2c, y1c, meta, used, Kc, dvals, avb, s), "router/dsqrelu");          // eq. (6)
+    STAGE(launch_transpose(W1, Kc, D, D, wcb, 1, nullptr, s, E, M), "router/W1[e].T");
+    STAGE(launch_spmm_blocked(avb, amb, wcb, nullptr, rows, D, Kc, 0, dxp, D, s, &g0), "router/dX");                      // eq. (7)
     STAGE(launch_venom_unpermute(dxp, row_of_token, T, D, dX, s), "router/unpermute(dX)");
     STAGE(launch_venom_expand_t_compact(dvals, meta, rows, Kc, at, s), "router/expand(dy1)");
     STAGE(launch_gemm_nt(0, at, nullptr, xpt, nullptr, Kc, D, rows, 0, dW1, D, s, &g2), "router/dW1");                    // eq. (8)

@@ -377,6 +377,10 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                     if (valid && t0 + t < Rb) {
                         *reinterpret_cast<uint32_t*>(ep.vals + (int64_t)(t0 + t) * (F / 2) + (f0 >> 1) + 2 * g) = v;
                         if ((g & 7) == 0) *reinterpret_cast<uint32_t*>(ep.meta + (int64_t)(t0 + t) * (F / 8) + (f0 >> 3) + (g >> 1)) = mw;
+                        if (ep.v24) {       // the same packed matrix in the blocked operand layout (A operand of eqs. (3), (7) over the expert's run)
+                            *reinterpret_cast<uint32_t*>(ep.v24 + blk_off(t0 + t, (f0 >> 1) + 2 * g, F / 64)) = v;
+                            if ((g & 3) == 0) *reinterpret_cast<uint16_t*>(ep.m24 + mblk_off(t0 + t, f0 + 4 * g, F / 64)) = (uint16_t)mw;
+                        }
                     }
                 }
             }

@@ -81,8 +81,10 @@ hipError_t launch_vnm_to_24(const uint16_t* vals, const uint8_t* meta, const uin
 hipError_t launch_vnm_expand_t(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
                                uint16_t* out, int blocked, hipStream_t s);
 // batch > 1: `batch` matrices [R, C] (ld = C) back to back, transposed one by one.
+// cluster_M (with batch = M / 4 experts, R = hidden units per expert): matrix e reads the rows of `in` that belong to expert e,
+// row r of it = row (r / 4) * M + 4 e + r % 4 of the one [F, C] source (Section 3.3's expert-major order).
 hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld, uint16_t* out, int blocked, uint16_t* out_same,
-                            hipStream_t s, int batch = 1);
+                            hipStream_t s, int batch = 1, int cluster_M = 0);
 
 // C[i, j] = sum_k A[i, k] * B[j, k]  (both operands K-contiguous).
 //   sparse_a: A given as 2:4 packed (a_vals [Ra, K/2], a_meta [Ra, K/8]) and multiplied on the
@@ -112,7 +114,7 @@ hipError_t launch_venom_permute(const int32_t* expert, int64_t T, int E, int64_t
 hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, int blocked, hipStream_t s);
 hipError_t launch_venom_unpermute(const uint16_t* src, const int32_t* row_of_token, int64_t T, int64_t D, uint16_t* out, hipStream_t s);
 hipError_t launch_venom_dsqrelu_compact(const uint16_t* dy2c, const uint16_t* y1c, const uint8_t* meta, int64_t rows, int64_t Kc,
-                                        uint16_t* dvals, hipStream_t s);
+                                        uint16_t* dvals, uint16_t* dvals_blk, hipStream_t s);
 hipError_t launch_venom_expand_t_compact(const uint16_t* vals, const uint8_t* meta, int64_t rows, int64_t Kc, uint16_t* at, hipStream_t s);
 hipError_t launch_fill_bytes(void* p, uint8_t v, size_t n_bytes, hipStream_t s);
 hipError_t launch_venom_colidx(const GemmGroup& g, int64_t cap, int64_t groups, uint8_t* colidx, hipStream_t s);

@@ -161,8 +161,8 @@ __global__ void __launch_bounds__(256) venom_unpermute_kernel(const uint16_t* __
 // eq. (6) on the compact arrays of the router's output: slot s of group g of row r sits at compact column 4 g + p_s
 // (p_s from the metadata nibble); dvals = bf16(2 * dy2c * max(y1c, 0)) there.  One thread per metadata byte (two groups).
 __global__ void __launch_bounds__(256) venom_dsqrelu_compact_kernel(const uint16_t* __restrict__ dy2c, const uint16_t* __restrict__ y1c,
-                                                                   const uint8_t* __restrict__ meta, int64_t n_bytes,
-                                                                   uint16_t* __restrict__ dvals) {
+                                                                   const uint8_t* __restrict__ meta, int64_t n_bytes, int Kc,
+                                                                   uint16_t* __restrict__ dvals, uint16_t* __restrict__ dvals_blk) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= n_bytes) return;
     const uint4 dv = *reinterpret_cast<const uint4*>(dy2c + idx * 8);
@@ -185,6 +185,11 @@ __global__ void __launch_bounds__(256) venom_dsqrelu_compact_kernel(const uint16
         o[g] = r[0] | (r[1] << 16);
     }
     *reinterpret_cast<uint2*>(dvals + idx * 4) = make_uint2(o[0], o[1]);
+    if (dvals_blk) {        // blocked operand layout of the packed [rows, Kc / 2] matrix
+        const int64_t r = idx / (Kc >> 3);
+        const int kk = (int)(idx - r * (Kc >> 3)) * 4;
+        *reinterpret_cast<uint2*>(dvals_blk + blk_off(r, kk, Kc >> 6)) = make_uint2(o[0], o[1]);
+    }
 }
 
 // (vals [rows, Kc / 2], meta [rows, Kc / 8]) -> the dense transposed matrix at[j, r] ([Kc, rows], row-major), zeros at the
@@ -280,9 +285,9 @@ hipError_t launch_venom_unpermute(const uint16_t* src, const int32_t* row_of_tok
 }
 
 hipError_t launch_venom_dsqrelu_compact(const uint16_t* dy2c, const uint16_t* y1c, const uint8_t* meta, int64_t rows, int64_t Kc,
-                                        uint16_t* dvals, hipStream_t s) {
+                                        uint16_t* dvals, uint16_t* dvals_blk, hipStream_t s) {
     const int64_t n = rows * (Kc / 8);
-    hipLaunchKernelGGL(venom_dsqrelu_compact_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dy2c, y1c, meta, n, dvals);
+    hipLaunchKernelGGL(venom_dsqrelu_compact_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dy2c, y1c, meta, n, (int)Kc, dvals, dvals_blk);
     return hipGetLastError();
 }
 
