@@ -167,7 +167,7 @@ int venom_expert_matmul(const sffn_cfg* cfg, const int64_t* seg_offsets, const u
                         uint8_t* colidx, void* workspace, size_t ws_bytes, void* stream);
 
 /* Alg. 1 + Alg. 2 with Alg. 3 as the activation sparsifier (Alg. 1 line 6, MoEToVenom): the whole training step of the
- * neuron-level router, given the routing of venom_route (seg_offsets: HOST array; perm, row_of_token: device).
+ * neuron-level router, given the routing of venom_route (seg_offsets: HOST array; perm: device).
  * Forward: y1c / V:N:M y2 as in venom_expert_matmul, Y3 = y2v W2.T (eq. (3), dense W2).  Backward: dy2 = dY sparsify24(W2.T)
  * evaluated at the routed expert's hidden units only (eq. (4)), eq. (6) on y2's slots, dX with the dense W1 (eq. (7)), and
  * both weight gradients (eqs. (5), (8)); every contraction is grouped by expert, so all six shrink with 4/M.  Y3, dX [T,D]
@@ -179,10 +179,9 @@ typedef struct {
 } sffn_router_layout;
 size_t sffn_router_workspace_bytes(const sffn_cfg* cfg);
 int    sffn_router_workspace_layout(const sffn_cfg* cfg, sffn_router_layout* out);
-int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const int32_t* row_of_token,
-                    const uint16_t* X, const uint16_t* W1, const uint16_t* W2, const float* b1, const uint16_t* dY,
-                    uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes,
-                    void* stream);
+int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* X,
+                    const uint16_t* W1, const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3,
+                    uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
 
 /* Alg. 1 + Alg. 2, one call: X [T,D], W1 [F,D], W2 [D,F], b1 fp32 [F] or NULL, dY [T,D] ->
  * Y3 [T,D], dX [T,D], dW1 [F,D], dW2 [D,F]; intermediates land in `workspace` at the offsets of

@@ -78,7 +78,7 @@ def load():
     lib.sffn_router_workspace_bytes.restype = sz
     lib.sffn_router_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg)]
     lib.sffn_router_workspace_layout.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_RouterLayout)]
-    lib.ffn_router_step.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(ctypes.c_int64)] + [p] * 11 + [p, sz, p]
+    lib.ffn_router_step.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(ctypes.c_int64)] + [p] * 10 + [p, sz, p]
     lib.sffn_profile_enable.argtypes = [i32]
     lib.sffn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_char_p), i32]
     _LIB = lib
@@ -370,7 +370,7 @@ class FfnRouterStep:
         """route: the dict venom_route returned for X."""
         E = self.M // 4
         seg_arr = (ctypes.c_int64 * (E + 1))(*[int(v) for v in route["seg"]])
-        _check(load().ffn_router_step(ctypes.byref(self.cfg), seg_arr, _ptr(route["perm"]), _ptr(route["row_of_token"]), _ptr(X), _ptr(W1),
+        _check(load().ffn_router_step(ctypes.byref(self.cfg), seg_arr, _ptr(route["perm"]), _ptr(X), _ptr(W1),
                                       _ptr(W2), _ptr(b1), _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2),
                                       _ptr(self.ws), self.layout["total"], _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2

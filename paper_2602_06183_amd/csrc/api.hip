@@ -304,7 +304,7 @@ int venom_expert_matmul(const sffn_cfg* cfg, const int64_t* seg_offsets, const u
     uint8_t* wm = ws;                                  ws += up256((size_t)F * D / 8);
     uint16_t* wvb = (uint16_t*)ws;                     ws += up256((size_t)F * D);
     uint8_t* wmb = ws;
-    LAUNCH(launch_venom_gather_x(X, perm, cap, D, xb, 1, s), "venom_expert_matmul/gather(X)");
+    LAUNCH(launch_venom_gather_x(X, perm, cap, D, xb, s), "venom_expert_matmul/gather(X)");
     LAUNCH(launch_prune24_step(W1, F, D, D, 0, cfg->mode, wv, wm, wvb, wmb, nullptr, s, 1, M), "venom_expert_matmul/prune24(W1)");
     LAUNCH(launch_venom_colidx(g, cap, F / M, colidx, s), "venom_expert_matmul/colidx");
     // rows past the last run are never touched by the grouped contraction: clear them (they are padding)
@@ -324,7 +324,7 @@ int venom_expert_matmul(const sffn_cfg* cfg, const int64_t* seg_offsets, const u
 namespace {
 struct RouterLayout {
     sffn_router_layout pub;
-    size_t xp, xpt, xb, dyp, dypt, dyb, w1cv, w1cm, w1cvb, w1cmb, w2t, w2cv, w2cm, w2cvb, w2cmb, at, y3p, dxp, avb, amb, wcb, total;
+    size_t xpt, xb, dypt, dyb, w1cv, w1cm, w1cvb, w1cmb, w2t, w2cv, w2cm, w2cvb, w2cmb, at, avb, amb, wcb, total;
 };
 bool make_router_layout(const sffn_cfg* c, RouterLayout* L) {
     if (!c || c->T <= 0 || !mult64(c->D) || !mult64(c->F) || !vnm_ok(c->V, c->M)) return false;
@@ -335,13 +335,12 @@ bool make_router_layout(const sffn_cfg* c, RouterLayout* L) {
     L->pub.y1c = take(rows * Kc * 2);      L->pub.vals = take(rows * Kc);          L->pub.meta = take(rows * Kc / 8);
     L->pub.colidx = take(rows / 64 * (F / M) * 4);
     L->pub.dy2c = take(rows * Kc * 2);     L->pub.dvals = take(rows * Kc);
-    L->xp = take(rows * D * 2);  L->xpt = take(rows * D * 2);  L->xb = take(rows * D * 2);
-    L->dyp = take(rows * D * 2); L->dypt = take(rows * D * 2); L->dyb = take(rows * D * 2);
+    L->xpt = take(rows * D * 2);  L->xb = take(rows * D * 2);
+    L->dypt = take(rows * D * 2); L->dyb = take(rows * D * 2);
     L->w1cv = take(F * D); L->w1cm = take(F * D / 8); L->w1cvb = take(F * D); L->w1cmb = take(F * D / 8);
     L->w2t = take(F * D * 2);
     L->w2cv = take(F * D); L->w2cm = take(F * D / 8); L->w2cvb = take(F * D); L->w2cmb = take(F * D / 8);
     L->at = take(rows * Kc * 2);
-    L->y3p = take(rows * D * 2); L->dxp = take(rows * D * 2);
     L->avb = take(rows * Kc); L->amb = take(rows * Kc / 8);     // packed activation (y2, then dy1) in the blocked operand layout
     L->wcb = take(F * D * 2);                                    // per expert: its slice of W2 (then of W1.T) as [D, Kc], blocked
     L->total = off; L->pub.total = off;
@@ -362,10 +361,10 @@ int sffn_router_workspace_layout(const sffn_cfg* cfg, sffn_router_layout* out) {
     return SFFN_OK;
 }
 
-int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const int32_t* row_of_token, const uint16_t* X,
+int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* X,
                     const uint16_t* W1, const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
                     uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
-    REQUIRE(cfg && seg_offsets && perm && row_of_token && X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_router_step: null pointer");
+    REQUIRE(cfg && seg_offsets && perm && X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_router_step: null pointer");
     REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "ffn_router_step: only V=64 with M in {8, 16, 32, 64} is built");
     RouterLayout L;
     REQUIRE(make_router_layout(cfg, &L), SFFN_EINVAL, "ffn_router_step: T > 0, D and F positive multiples of 64, 4F/M a multiple of 64");
@@ -375,7 +374,7 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
     const int64_t Kc = 4 * F / M, rows = sffn_venom_rows(T, M);
     REQUIRE(rows < 65536 * 64 && fits_int(F) && fits_int(D) && fits_int(rows * (D / 8)) && fits_int(rows * (Kc / 8)), SFFN_EUNSUPPORTED,
             "ffn_router_step: dimension too large");
-    REQUIRE(aligned16(perm) && aligned16(row_of_token) && aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(b1) && aligned16(dY) &&
+    REQUIRE(aligned16(perm) && aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(b1) && aligned16(dY) &&
                 aligned16(Y3) && aligned16(dX) && aligned16(dW1) && aligned16(dW2) && aligned16(workspace), SFFN_EINVAL,
             "ffn_router_step: pointers must be 16-byte aligned");
     REQUIRE(workspace && ws_bytes >= L.total, SFFN_EWORKSPACE, "ffn_router_step: workspace missing or too small");
@@ -388,6 +387,7 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
     g1.a_stride = Kc * D / 2; g1.m_stride = Kc * D / 8; g1.bias_stride = 4;
     GemmGroup g0 = g1;                                  // eqs. (3), (7): token runs along i, the expert's [D, Kc] weight slice as B
     g0.role = 0; g0.a_stride = g0.m_stride = g0.bias_stride = 0; g0.b_stride = D * Kc;
+    g0.out_row_map = perm;                              // results go straight to token order; padding rows are not stored
     GemmGroup g2 = g1;                                  // weight gradients: every expert contracts over its own run
     g2.role = 2; g2.a_stride = g2.m_stride = g2.bias_stride = 0; g2.out_stride = 0;
     const int logM = M == 8 ? 3 : M == 16 ? 4 : M == 32 ? 5 : 6;
@@ -398,19 +398,17 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
     unsigned char* ws = (unsigned char*)workspace;
     uint16_t* y1c = (uint16_t*)(ws + L.pub.y1c);   uint16_t* vals = (uint16_t*)(ws + L.pub.vals);   uint8_t* meta = ws + L.pub.meta;
     uint8_t* colidx = ws + L.pub.colidx;           uint16_t* dy2c = (uint16_t*)(ws + L.pub.dy2c);   uint16_t* dvals = (uint16_t*)(ws + L.pub.dvals);
-    uint16_t* xp = (uint16_t*)(ws + L.xp);   uint16_t* xpt = (uint16_t*)(ws + L.xpt);   uint16_t* xb = (uint16_t*)(ws + L.xb);
-    uint16_t* dyp = (uint16_t*)(ws + L.dyp); uint16_t* dypt = (uint16_t*)(ws + L.dypt); uint16_t* dyb = (uint16_t*)(ws + L.dyb);
+    uint16_t* xpt = (uint16_t*)(ws + L.xpt);   uint16_t* xb = (uint16_t*)(ws + L.xb);
+    uint16_t* dypt = (uint16_t*)(ws + L.dypt); uint16_t* dyb = (uint16_t*)(ws + L.dyb);
     uint16_t* w1cv = (uint16_t*)(ws + L.w1cv); uint8_t* w1cm = ws + L.w1cm; uint16_t* w1cvb = (uint16_t*)(ws + L.w1cvb); uint8_t* w1cmb = ws + L.w1cmb;
     uint16_t* w2t = (uint16_t*)(ws + L.w2t);
     uint16_t* w2cv = (uint16_t*)(ws + L.w2cv); uint8_t* w2cm = ws + L.w2cm; uint16_t* w2cvb = (uint16_t*)(ws + L.w2cvb); uint8_t* w2cmb = ws + L.w2cmb;
     uint16_t* at = (uint16_t*)(ws + L.at);
-    uint16_t* y3p = (uint16_t*)(ws + L.y3p); uint16_t* dxp = (uint16_t*)(ws + L.dxp);
     uint16_t* avb = (uint16_t*)(ws + L.avb); uint8_t* amb = ws + L.amb; uint16_t* wcb = (uint16_t*)(ws + L.wcb);
 
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
     // ---- Alg. 1 with Alg. 3 as the sparsifier ---------------------------------------------------------------------
-    STAGE(launch_venom_gather_x(X, perm, rows, D, xp, 0, s), "router/gather(X)");
-    STAGE(launch_transpose(xp, rows, D, D, xpt, 0, xb, s), "router/X.T");
+    STAGE(launch_transpose(X, rows, D, D, xpt, 0, xb, s, 1, 0, perm), "router/X[perm].T");     // permuted rows: transposed (eq. (8)) and blocked (eq. (1))
     STAGE(launch_prune24_step(W1, F, D, D, 0, cfg->mode, w1cv, w1cm, w1cvb, w1cmb, nullptr, s, 1, M), "router/prune24(W1)");
     STAGE(launch_venom_colidx(g1, rows, F / M, colidx, s), "router/colidx");
     if (used < rows) {      // rows past the last run are padding that no contraction writes
@@ -431,14 +429,15 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
     }
     STAGE(launch_transpose(W2, D, F, F, w2t, 0, nullptr, s), "router/W2.T");
     STAGE(launch_transpose(w2t, Kc, D, D, wcb, 1, nullptr, s, E, M), "router/W2[:,e]");
-    STAGE(launch_spmm_blocked(avb, amb, wcb, nullptr, rows, D, Kc, 0, y3p, D, s, &g0), "router/y3");                      // eq. (3)
-    STAGE(launch_venom_unpermute(y3p, row_of_token, T, D, Y3, s), "router/unpermute(y3)");
+    STAGE(launch_spmm_blocked(avb, amb, wcb, nullptr, rows, D, Kc, 0, Y3, D, s, &g0), "router/y3");                       // eq. (3)
     // ---- Alg. 2 ------------------------------------------------------------------------------------------------------
     STAGE(launch_prune24_step(w2t, F, D, D, 0, cfg->mode, w2cv, w2cm, w2cvb, w2cmb, nullptr, s, 1, M), "router/prune24(W2.T)");
-    STAGE(launch_venom_gather_x(dY, perm, rows, D, dyp, 0, s), "router/gather(dY)");
-    STAGE(launch_transpose(dyp, rows, D, D, dypt, 0, dyb, s), "router/dY.T");
+    STAGE(launch_transpose(dY, rows, D, D, dypt, 0, dyb, s, 1, 0, perm), "router/dY[perm].T");
     STAGE(launch_venom_expand_t_compact(vals, meta, rows, Kc, at, s), "router/expand(y2)");
-    STAGE(launch_gemm_nt(0, at, nullptr, dypt, nullptr, Kc, D, rows, 1, dW2, F, s, &g2), "router/dW2");                   // eq. (5)
+    // eq. (5) is computed as dW2.T [F, D] (whole 2 D-byte rows per hidden unit) and transposed: writing dW2 [D, F] directly
+    // would scatter 8-byte pieces M hidden units apart
+    STAGE(launch_gemm_nt(0, at, nullptr, dypt, nullptr, Kc, D, rows, 0, wcb, D, s, &g2), "router/dW2.T");                 // eq. (5)
+    STAGE(launch_transpose(wcb, F, D, D, dW2, 0, nullptr, s), "router/dW2");
     {
         GemmGroup g4 = g1;
         g4.bias_stride = 0;
@@ -447,8 +446,7 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
     }
     if (used > 0) STAGE(launch_venom_dsqrelu_compact(dy2c, y1c, meta, used, Kc, dvals, avb, s), "router/dsqrelu");          // eq. (6)
     STAGE(launch_transpose(W1, Kc, D, D, wcb, 1, nullptr, s, E, M), "router/W1[e].T");
-    STAGE(launch_spmm_blocked(avb, amb, wcb, nullptr, rows, D, Kc, 0, dxp, D, s, &g0), "router/dX");                      // eq. (7)
-    STAGE(launch_venom_unpermute(dxp, row_of_token, T, D, dX, s), "router/unpermute(dX)");
+    STAGE(launch_spmm_blocked(avb, amb, wcb, nullptr, rows, D, Kc, 0, dX, D, s, &g0), "router/dX");                       // eq. (7)
     STAGE(launch_venom_expand_t_compact(dvals, meta, rows, Kc, at, s), "router/expand(dy1)");
     STAGE(launch_gemm_nt(0, at, nullptr, xpt, nullptr, Kc, D, rows, 0, dW1, D, s, &g2), "router/dW1");                    // eq. (8)
     return SFFN_OK;

@@ -507,8 +507,9 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                 const int e = lane + 64 * p, row = e / CH, ch = e % CH;
                 const int i = i0 + wm * WM + a * 32 + row, j = j0 + wn * WN + ch * 8;
                 if (i < Ra && j < Rb) {
-                    const int64_t io = grp.map_logM ? ((int64_t)(i >> 2) << grp.map_logM) + 4 * expert_id + (i & 3) : i;
-                    *reinterpret_cast<uint4*>(out + io * ldo + j) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
+                    int64_t io = grp.map_logM ? ((int64_t)(i >> 2) << grp.map_logM) + 4 * expert_id + (i & 3) : i;
+                    if (grp.out_row_map) io = grp.out_row_map[i];
+                    if (io >= 0) *reinterpret_cast<uint4*>(out + io * ldo + j) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
                 }
             }
             __syncthreads();

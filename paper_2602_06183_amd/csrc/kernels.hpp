@@ -46,6 +46,8 @@ struct GemmGroup {
     // role 2 on row-major operands (weight gradients of the neuron-level experts, Section 3.3): output index i of expert e is
     // compact column i of its hidden units and lands at hidden unit (i / 4) * M + 4 e + i % 4 of the one shared output (0: off)
     int map_logM = 0;
+    // roles 0 / none with the i-major output: row i goes to row out_row_map[i] of the output (negative: not stored)
+    const int32_t* out_row_map = nullptr;
     int32_t seg[kMaxExperts + 1] = {0};
 };
 
@@ -83,8 +85,9 @@ hipError_t launch_vnm_expand_t(const uint16_t* vals, const uint8_t* meta, const 
 // batch > 1: `batch` matrices [R, C] (ld = C) back to back, transposed one by one.
 // cluster_M (with batch = M / 4 experts, R = hidden units per expert): matrix e reads the rows of `in` that belong to expert e,
 // row r of it = row (r / 4) * M + 4 e + r % 4 of the one [F, C] source (Section 3.3's expert-major order).
+// in_perm (batch = 1): row r of the [R, C] matrix is row in_perm[r] of `in` (a negative entry: a zero row).
 hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld, uint16_t* out, int blocked, uint16_t* out_same,
-                            hipStream_t s, int batch = 1, int cluster_M = 0);
+                            hipStream_t s, int batch = 1, int cluster_M = 0, const int32_t* in_perm = nullptr);
 
 // C[i, j] = sum_k A[i, k] * B[j, k]  (both operands K-contiguous).
 //   sparse_a: A given as 2:4 packed (a_vals [Ra, K/2], a_meta [Ra, K/8]) and multiplied on the
@@ -111,8 +114,7 @@ hipError_t launch_venom_route(const uint16_t* X, const uint16_t* means, int64_t 
                               hipStream_t s);
 hipError_t launch_venom_permute(const int32_t* expert, int64_t T, int E, int64_t cap, int32_t* blockcnt, int32_t* seg, int32_t* perm,
                                 int32_t* row_of_token, hipStream_t s);
-hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, int blocked, hipStream_t s);
-hipError_t launch_venom_unpermute(const uint16_t* src, const int32_t* row_of_token, int64_t T, int64_t D, uint16_t* out, hipStream_t s);
+hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, hipStream_t s);
 hipError_t launch_venom_dsqrelu_compact(const uint16_t* dy2c, const uint16_t* y1c, const uint8_t* meta, int64_t rows, int64_t Kc,
                                         uint16_t* dvals, uint16_t* dvals_blk, hipStream_t s);
 hipError_t launch_venom_expand_t_compact(const uint16_t* vals, const uint8_t* meta, int64_t rows, int64_t Kc, uint16_t* at, hipStream_t s);

@@ -133,9 +133,9 @@ __global__ void __launch_bounds__(256) venom_scatter_kernel(const int32_t* __res
     }
 }
 
-// X rows in permuted order (zero rows for padding), blocked operand layout or row-major: one thread per 16 bytes.
+// X rows in permuted order (zero rows for padding), blocked operand layout: one thread per 16 bytes.
 __global__ void __launch_bounds__(256) venom_gather_x_kernel(const uint16_t* __restrict__ X, const int32_t* __restrict__ perm, int cap, int D,
-                                                            uint16_t* __restrict__ xb, int blocked) {
+                                                            uint16_t* __restrict__ xb) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int cpr = D >> 3;
     const int64_t r = idx / cpr;
@@ -144,18 +144,7 @@ __global__ void __launch_bounds__(256) venom_gather_x_kernel(const uint16_t* __r
     const int t = perm[r];
     uint4 v = make_uint4(0, 0, 0, 0);
     if (t >= 0) v = *reinterpret_cast<const uint4*>(X + (int64_t)t * D + c * 8);
-    *reinterpret_cast<uint4*>(xb + (blocked ? blk_off(r, c * 8, D >> 5) : r * D + c * 8)) = v;
-}
-
-// out[t, :] = src[row_of_token[t], :]: results of the permuted row order back in token order.
-__global__ void __launch_bounds__(256) venom_unpermute_kernel(const uint16_t* __restrict__ src, const int32_t* __restrict__ row_of_token, int T, int D,
-                                                             uint16_t* __restrict__ out) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int cpr = D >> 3;
-    const int64_t t = idx / cpr;
-    const int c = (int)(idx - t * cpr);
-    if (t >= T) return;
-    *reinterpret_cast<uint4*>(out + t * D + c * 8) = *reinterpret_cast<const uint4*>(src + (int64_t)row_of_token[t] * D + c * 8);
+    *reinterpret_cast<uint4*>(xb + blk_off(r, c * 8, D >> 5)) = v;
 }
 
 // eq. (6) on the compact arrays of the router's output: slot s of group g of row r sits at compact column 4 g + p_s
@@ -272,15 +261,9 @@ hipError_t launch_venom_permute(const int32_t* expert, int64_t T, int E, int64_t
     return hipGetLastError();
 }
 
-hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, int blocked, hipStream_t s) {
+hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, hipStream_t s) {
     const int64_t n = cap * (D / 8);
-    hipLaunchKernelGGL(venom_gather_x_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, X, perm, (int)cap, (int)D, xb, blocked);
-    return hipGetLastError();
-}
-
-hipError_t launch_venom_unpermute(const uint16_t* src, const int32_t* row_of_token, int64_t T, int64_t D, uint16_t* out, hipStream_t s) {
-    const int64_t n = T * (D / 8);
-    hipLaunchKernelGGL(venom_unpermute_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, row_of_token, (int)T, (int)D, out);
+    hipLaunchKernelGGL(venom_gather_x_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, X, perm, (int)cap, (int)D, xb);
     return hipGetLastError();
 }
 

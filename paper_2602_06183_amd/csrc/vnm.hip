@@ -177,7 +177,8 @@ __global__ void __launch_bounds__(256) vnm_expand_t_kernel(const uint16_t* __res
 // blocked = 1: out (the transpose) and, when given, out_same (a copy of `in`) are written in the blocked
 // operand layout instead of row-major.
 __global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* __restrict__ in, int64_t R, int64_t C, int64_t ld,
-                                                            uint16_t* __restrict__ out, int blocked, uint16_t* __restrict__ out_same, int map_logM) {
+                                                            uint16_t* __restrict__ out, int blocked, uint16_t* __restrict__ out_same, int map_logM,
+                                                            const int32_t* __restrict__ in_perm) {
     __shared__ __attribute__((aligned(16))) uint16_t tile[64][64 + 2];
     const int tid = threadIdx.x;
     const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
@@ -192,7 +193,9 @@ __global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* __r
         const int e = tid + 256 * i, rr = e >> 3, seg = e & 7;
         int64_t rs = r0 + rr;
         if (map_logM) rs = ((rs >> 2) << map_logM) + 4 * blockIdx.z + (rs & 3);
-        const uint4 w = *reinterpret_cast<const uint4*>(in + rs * ld + c0 + seg * 8);
+        if (in_perm) rs = in_perm[rs];                       // row r of the matrix is row in_perm[r] of `in`; negative: a zero row
+        uint4 w = make_uint4(0, 0, 0, 0);
+        if (rs >= 0) w = *reinterpret_cast<const uint4*>(in + rs * ld + c0 + seg * 8);
         uint32_t* p = reinterpret_cast<uint32_t*>(&tile[rr][seg * 8]);
         p[0] = w.x; p[1] = w.y; p[2] = w.z; p[3] = w.w;
     }
@@ -249,13 +252,14 @@ hipError_t launch_vnm_expand_t(const uint16_t* vals, const uint8_t* meta, const 
 }
 
 hipError_t launch_transpose(const uint16_t* in, int64_t R, int64_t C, int64_t ld, uint16_t* out, int blocked, uint16_t* out_same,
-                            hipStream_t s, int batch, int cluster_M) {
+                            hipStream_t s, int batch, int cluster_M, const int32_t* in_perm) {
     if (batch > 1 && ld != C) return hipErrorInvalidValue;
+    if (in_perm && (batch > 1 || cluster_M)) return hipErrorInvalidValue;
     if (cluster_M && batch * 4 != cluster_M) return hipErrorInvalidValue;
     const int logM = cluster_M == 8 ? 3 : cluster_M == 16 ? 4 : cluster_M == 32 ? 5 : cluster_M == 64 ? 6 : 0;
     if (cluster_M && !logM) return hipErrorInvalidValue;
     dim3 grid((unsigned)(C / 64), (unsigned)(R / 64), (unsigned)batch);
-    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, in, R, C, ld, out, blocked, out_same, logM);
+    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, in, R, C, ld, out, blocked, out_same, logM, in_perm);
     return hipGetLastError();
 }
 
