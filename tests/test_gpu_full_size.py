@@ -238,3 +238,52 @@ def test_full_size_router(M):
             dense = oracle.vnm_decompress(ov, om, oc, 64, M)
             assert_gemm_close(y3[real], oracle.dense_nt(dense[real - 64 * tb], inp["W2"]), "y3 rows")
         assert Kc == y1c.shape[1]
+
+
+@pytest.mark.parametrize("M", [16, 64])
+def test_full_size_router_step(M):
+    """ffn_router_step at the 1B shape as bench.py --router times it: routing bit-exact in full; packing and eq. (6)
+    bit-exact on sampled 64-row blocks from the GPU's own y1c / dy2c; every contraction on sampled rows / hidden units."""
+    from workload import make_router_inputs
+    T, D, F = CONFIGS["1b"]
+    inp = make_router_inputs(T, D, F, M, seed=0)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    route = sffn.venom_route(dev["X"], dev["means"], M)
+    step = sffn.FfnRouterStep(T, D, F, M)
+    outs = step(route, dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    torch.cuda.synchronize()
+    Y3, dX, dW1, dW2 = (to_bits(t) for t in outs)
+    sv = {k: to_bits(v) for k, v in step.saved().items()}
+    expert = oracle.route_top1(oracle.route_scores(inp["X"], inp["means"]))
+    perm, seg = oracle.expert_permutation(expert, M // 4)
+    assert np.array_equal(to_bits(route["perm"]), perm) and route["seg"] == [int(v) for v in seg]
+    rng = np.random.default_rng(5 + M)
+    w1s = oracle.prune24_dense(inp["W1"])
+    w2t_s = oracle.prune24_dense(np.ascontiguousarray(inp["W2"].T))
+    for tb in sorted(set(int(b) for b in rng.choice(int(seg[-1]) // 64, 5, replace=False)) | {0}):
+        rows = np.arange(64 * tb, 64 * tb + 64)
+        e = int(np.searchsorted(seg, 64 * tb, side="right") - 1)
+        cl = oracle.cluster_rows(e, M, F)
+        lseg = np.clip(seg - 64 * tb, 0, 64)
+        ov, om, oc = oracle.venom_from_compact(sv["y1c"][rows], perm[rows], lseg, M)
+        assert np.array_equal(sv["colidx"][tb:tb + 1], oc) and np.array_equal(sv["meta"][rows], om) and np.array_equal(sv["vals"][rows], ov)
+        dv = oracle.dsqrelu_vnm(oracle.scatter_compact(sv["dy2c"][rows], lseg, M, F), oracle.scatter_compact(sv["y1c"][rows], lseg, M, F), om, oc, 64, M)
+        assert np.array_equal(sv["dvals"][rows], dv)
+        sel = rows[perm[rows] >= 0][:8]
+        if len(sel) == 0:
+            continue
+        tok = perm[sel]
+        ref = oracle.bits_to_f64(inp["X"][tok]) @ oracle.bits_to_f64(w1s[cl]).T + inp["b1"].astype(np.float64)[cl][None, :]
+        assert_gemm_close(sv["y1c"][sel], oracle.f64_to_bits(ref), "y1c rows")
+        assert_gemm_close(sv["dy2c"][sel], oracle.dense_nt(inp["dY"][tok], w2t_s[cl]), "dy2c rows")
+        assert_gemm_close(Y3[tok], oracle.dense_nt(oracle.vnm_decompress(ov, om, oc, 64, M)[sel - 64 * tb], inp["W2"]), "y3 rows")
+        assert_gemm_close(dX[tok], oracle.dense_nt(oracle.vnm_decompress(dv, om, oc, 64, M)[sel - 64 * tb], np.ascontiguousarray(inp["W1"].T)), "dX rows")
+    # weight gradients: a few hidden units of two experts, contracted over the expert's whole run
+    for e in (0, M // 4 - 1):
+        run = np.arange(int(seg[e]), int(seg[e + 1]))
+        real = run[perm[run] >= 0]
+        js = np.sort(rng.choice(4 * F // M, 8, replace=False))
+        f = oracle.cluster_rows(e, M, F)[js]
+        for packed, G, got in ((sv["vals"], inp["dY"], np.ascontiguousarray(dW2[:, f].T)), (sv["dvals"], inp["X"], dW1[f])):
+            a = oracle.bits_to_f64(oracle.prune24_decompress(packed[real], sv["meta"][real])[:, js])
+            assert_gemm_close(got, oracle.f64_to_bits(a.T @ oracle.bits_to_f64(G[perm[real]])), "wgrad rows")
