@@ -24,7 +24,7 @@ def algorithmic_flops(stage, T, D, F, M=8):
     tdf = float(T) * D * F
     act = 4.0 / M * tdf                                          # V:2:M activations: 2 of M survive (M = 8: a quarter)
     if stage.startswith("router/"):                              # neuron-level experts: every contraction covers 4 / M of the hidden units
-        return act if stage in ("router/y1c+sqrelu+2:4", "router/dy2c", "router/y3", "router/dX", "router/dW2", "router/dW1") else None
+        return act if stage in ("router/y1c+sqrelu+2:4", "router/dy2c", "router/y3", "router/dX", "router/dW2.T", "router/dW1") else None
     return {"step/y1+sqrelu_vnm_compress": tdf, "step/dy2+dsqrelu_vnm": tdf, "step/y1": tdf, "step/dy2": tdf,   # 2:4 weights: half of K survives
             "step/y3": act, "step/dX": act, "step/dW2": act, "step/dW1": act}.get(stage)
 
@@ -33,7 +33,7 @@ def executed_flops(stage, T, D, F, M=8):
     """Flops the matrix cores are issued for (dense-equivalent of the instructions used)."""
     tdf = float(T) * D * F
     if stage.startswith("router/"):
-        return 8.0 / M * tdf if stage in ("router/y1c+sqrelu+2:4", "router/dy2c", "router/y3", "router/dX", "router/dW2", "router/dW1") else None
+        return 8.0 / M * tdf if stage in ("router/y1c+sqrelu+2:4", "router/dy2c", "router/y3", "router/dX", "router/dW2.T", "router/dW1") else None
     return {"step/y1+sqrelu_vnm_compress": 2 * tdf, "step/dy2+dsqrelu_vnm": 2 * tdf, "step/y1": 2 * tdf, "step/dy2": 2 * tdf,
             "step/y3": 2 * tdf, "step/dX": 2 * tdf, "step/dW2": 2 * tdf, "step/dW1": 2 * tdf}.get(stage)
 
@@ -43,8 +43,8 @@ KERNEL_OF_STAGE = {"step/y1+sqrelu_vnm_compress": "gemm_nt_v2_kernel<sparse A, s
                    "step/y3": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dX": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
                    "step/dW2": "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>", "step/dW1": "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>",
                    "router/y1c+sqrelu+2:4": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "router/dy2c": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
-                   "router/y3": "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>", "router/dX": "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>",
-                   "router/dW2": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>", "router/dW1": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>"}
+                   "router/y3": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "router/dX": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
+                   "router/dW2.T": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>", "router/dW1": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>"}
 
 
 def main():
@@ -256,16 +256,16 @@ def main():
         from workload import make_router_inputs   # only the expert means are new; X, W1, b1 are the step's
         router = {"dense_y1_ms": round(ms_of(lambda: torch.addmm(b1h, X, W1.t(), out=y1)), 4)}
         for m in (8, 16, 32, 64):
-            means = dev(make_router_inputs(64, D, 4 * m, m, seed=0)["means"])
-            t_route = ms_of(lambda: sffn.venom_route_launch(X, means, m))
-            rr = sffn.venom_route(X, means, m)
+            means_m = dev(make_router_inputs(64, D, 4 * m, m, seed=0)["means"])
+            t_route = ms_of(lambda: sffn.venom_route_launch(X, means_m, m))
+            rr = sffn.venom_route(X, means_m, m)
             ws_r = torch.empty((sffn.load().sffn_venom_matmul_workspace_bytes(T, D, F, m),), dtype=torch.uint8, device="cuda")
             t_mm = ms_of(lambda: sffn.venom_expert_matmul(X, rr["perm"], rr["seg"], W1, b1, m, mode, keep_y1c=False, workspace=ws_r))
             router["64:2:%d" % m] = {"experts": m // 4, "rows": int(rr["perm"].shape[0]), "route_and_group_ms": round(t_route, 4),
                                      "route_and_group_GBs_of_X": round(T * D * 2 / (t_route * 1e-3) / 1e9, 1),
                                      "gather_prune_matmul_ms": round(t_mm, 4),
                                      "conversion_vs_dense_y1": round(router["dense_y1_ms"] / (t_route + t_mm), 3)}
-            del ws_r, rr, means
+            del ws_r, rr, means_m
 
     # ---- how much of the activation's L1 mass the V:N:M format keeps (sum of kept y2 / sum of all y2): one extra,
     #      untimed step that also stores the dense y1; plain torch reductions, measurement only ------------------
