@@ -178,6 +178,8 @@ def main():
             acc[name] = acc.get(name, 0.0) + ms / nprof
     sffn.profile_enable(False)
     by_kernel = {}
+    if "step/dX" in acc and "step/W1.T" not in acc and M == 8:      # eq. (7) ran on the gathered-row kernel (no transpose of W1 in the step)
+        KERNEL_OF_STAGE["step/dX"] = "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>"
     if M != 8:      # the wide-block path contracts the expanded activation with the dense-operand variant of the tile kernel
         KERNEL_OF_STAGE.update({"step/dW2": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>", "step/dW1": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>"})
     for name, ms in acc.items():
