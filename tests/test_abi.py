@@ -107,6 +107,20 @@ def test_router_entry_points_validate_on_the_host():
     assert lib.venom_expert_matmul(ctypes.byref(cfg), seg(0, 64, 128, 256, 448), *tail, fake, big, None) == -1   # beyond the row capacity (384)
     bad = binding._Cfg(100, 64, 640, 64, 16, 0, 0)
     assert lib.venom_expert_matmul(ctypes.byref(bad), ok, *tail, fake, big, None) == -1
+    # the router's whole step: same host-side checks, plus its workspace layout
+    args = [fake] * 10
+    assert lib.sffn_router_workspace_bytes(ctypes.byref(cfg)) > 0 and lib.sffn_router_workspace_bytes(ctypes.byref(bad)) == 0
+    lay = binding._RouterLayout()
+    assert lib.sffn_router_workspace_layout(ctypes.byref(cfg), ctypes.byref(lay)) == 0
+    offs = [getattr(lay, n) for n in ("y1c", "vals", "meta", "colidx", "dy2c", "dvals")]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs) and lay.total == lib.sffn_router_workspace_bytes(ctypes.byref(cfg))
+    assert lib.ffn_router_step(ctypes.byref(cfg), ok, *args, fake, 16, None) == -3
+    assert lib.ffn_router_step(ctypes.byref(cfg), None, *args, fake, big, None) == -1
+    assert lib.ffn_router_step(ctypes.byref(cfg), seg(0, 64, 100, 128, 192), *args, fake, big, None) == -1
+    assert lib.ffn_router_step(ctypes.byref(cfg), seg(0, 64, 128, 256, 448), *args, fake, big, None) == -1
+    assert lib.ffn_router_step(ctypes.byref(bad), ok, *args, fake, big, None) == -1
+    m12 = binding._Cfg(100, 64, 1024, 64, 12, 0, 0)
+    assert lib.ffn_router_step(ctypes.byref(m12), ok, *args, fake, big, None) == -2
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
