@@ -129,8 +129,7 @@ int sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, int V, int M, 
     REQUIRE(aligned16(y1) && aligned16(vals) && aligned16(meta) && aligned16(colidx), SFFN_EINVAL,
             "sqrelu_vnm_compress: pointers must be 16-byte aligned");
     REQUIRE(fits_int(T) && fits_int(F) && T / 64 < 65536, SFFN_EUNSUPPORTED, "sqrelu_vnm_compress: T too large");
-    if (M == 8) LAUNCH(launch_sqrelu_vnm_compress(y1, T, F, vals, meta, colidx, (hipStream_t)stream), "sqrelu_vnm_compress");
-    else        LAUNCH(launch_sqrelu_vnm_compress_m(y1, T, F, M, vals, meta, colidx, (hipStream_t)stream), "sqrelu_vnm_compress");
+    LAUNCH(launch_sqrelu_vnm_compress_m(y1, T, F, M, vals, meta, colidx, (hipStream_t)stream), "sqrelu_vnm_compress");
     return SFFN_OK;
 }
 

@@ -53,8 +53,6 @@ struct GemmGroup {
 
 hipError_t launch_prune24(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
                           uint8_t* meta, hipStream_t stream);
-hipError_t launch_sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, uint16_t* vals, uint8_t* meta,
-                                      uint8_t* colidx, hipStream_t s);
 hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, const uint8_t* colidx,
                               int64_t T, int64_t F, uint16_t* dvals, hipStream_t s);
 // 2:4 prune-and-pack for the fused step: canonical outputs plus the blocked copies the GEMMs read;
@@ -63,7 +61,7 @@ hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uin
 hipError_t launch_prune24_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
                                uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream, int batch = 1,
                                int cluster_M = 0);   // cluster_M (trans = 0): rows come out expert-major, see prune24.hip
-// Wider blocks, M in {16, 32, 64} (vnm_general.hip): same operations and packed layout as the M = 8 kernels.
+// vnm_general.hip: the stand-alone compressor for M in {8, 16, 32, 64}, and eq. (6) / 2:4 re-expression / transposed expansion for M in {16, 32, 64}.
 hipError_t launch_sqrelu_vnm_compress_m(const uint16_t* y1, int64_t T, int64_t F, int M, uint16_t* vals, uint8_t* meta, uint8_t* colidx,
                                         hipStream_t s);
 hipError_t launch_dsqrelu_vnm_m(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,

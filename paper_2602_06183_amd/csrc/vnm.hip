@@ -1,7 +1,6 @@
-// V:N:M (V=64, N=2, M=8) kernels: SquaredReLU + on-the-fly compression of the hidden activation
-// (paper eq. (2), Section 2.3, Alg. 1 lines 5-6), eq. (6) on the kept slots (Alg. 2 line 4), and the
-// layout helpers the GEMMs consume (re-expression as plain 2:4 over all columns, dense transposed
-// expansion, bf16 transpose).  All of them are HBM-bound scans.
+// V:N:M (V=64, N=2, M=8) kernels: eq. (6) on the kept slots (Alg. 2 line 4) and the layout helpers the GEMMs
+// consume (re-expression as plain 2:4 over all columns, dense transposed expansion, bf16 transpose).  All of them
+// are HBM-bound scans.  The stand-alone compressor of eq. (2) + Section 2.3 lives in vnm_general.hip, for every M.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -11,89 +10,6 @@ __device__ __forceinline__ uint32_t pick16(const uint32_t (&w)[4], uint32_t c) {
     const uint32_t d = c >> 1;
     const uint32_t lo = (d == 0) ? w[0] : (d == 1) ? w[1] : (d == 2) ? w[2] : w[3];
     return (c & 1u) ? (lo >> 16) : (lo & 0xFFFFu);
-}
-
-__device__ __forceinline__ uint32_t sqrelu_pair(uint32_t w) {
-    const float a = bf2f(w & 0xFFFFu), b = bf2f(w >> 16);
-    const float ra = a > 0.0f ? a : 0.0f, rb = b > 0.0f ? b : 0.0f;
-    return f2bf2(ra * ra, rb * rb);
-}
-
-// One workgroup = 64 rows (one V block) x 64 column blocks (512 columns).  Wave w holds rows
-// 16w..16w+15 of every block in registers as y2; the column scores are a strict left-to-right
-// fp32 sum over the 64 rows, so the four waves add their rows one after the other, handing the
-// running sums over through LDS.  Lane = column block, so every HBM access of a wave is one
-// contiguous 1 KB (loads), 256 B (values) or 32 B (metadata) run.
-__global__ void __launch_bounds__(256) sqrelu_vnm_compress_kernel(const uint16_t* __restrict__ y1, int64_t F, int nblk,
-                                                                 uint16_t* __restrict__ vals, uint8_t* __restrict__ meta,
-                                                                 uint8_t* __restrict__ colidx) {
-    __shared__ float s_score[8][64];
-    __shared__ uint32_t s_col[64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int blk = blockIdx.x * 64 + lane;
-    const bool active = blk < nblk;
-    const int64_t tb = blockIdx.y;
-    const int64_t row0 = tb * 64 + wave * 16;
-
-    uint32_t y2[16][4];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        uint4 w = make_uint4(0, 0, 0, 0);
-        if (active) w = *reinterpret_cast<const uint4*>(y1 + (row0 + i) * F + (int64_t)blk * 8);
-        y2[i][0] = sqrelu_pair(w.x); y2[i][1] = sqrelu_pair(w.y);
-        y2[i][2] = sqrelu_pair(w.z); y2[i][3] = sqrelu_pair(w.w);
-    }
-
-    // ordered score chain: wave 0 rows 0-15, wave 1 rows 16-31, ...
-    for (int turn = 0; turn < 4; ++turn) {
-        if (wave == turn) {
-            float sc[8];
-#pragma unroll
-            for (int c = 0; c < 8; ++c) sc[c] = (turn == 0) ? 0.0f : s_score[c][lane];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    sc[2 * d] = sc[2 * d] + bf2f(y2[i][d] & 0xFFFFu);
-                    sc[2 * d + 1] = sc[2 * d + 1] + bf2f(y2[i][d] >> 16);
-                }
-            }
-            if (turn < 3) {
-#pragma unroll
-                for (int c = 0; c < 8; ++c) s_score[c][lane] = sc[c];
-            } else {
-                // four largest scores, ties to the lower column; offsets stored ascending
-                uint32_t packed = 0, n = 0;
-#pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    int rank = 0;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        if (j < c) rank += (sc[j] >= sc[c]);
-                        else if (j > c) rank += (sc[j] > sc[c]);
-                    }
-                    if (rank < 4) { packed |= (uint32_t)c << (8 * n); ++n; }
-                }
-                s_col[lane] = packed;
-                if (active) *reinterpret_cast<uint32_t*>(colidx + (tb * nblk + blk) * 4) = packed;
-            }
-        }
-        __syncthreads();
-    }
-
-    const uint32_t cw = s_col[lane];
-    const uint32_t c0 = cw & 0xFFu, c1 = (cw >> 8) & 0xFFu, c2 = (cw >> 16) & 0xFFu, c3 = cw >> 24;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        uint32_t nib;
-        const uint32_t v = select24<false>(pick16(y2[i], c0), pick16(y2[i], c1), pick16(y2[i], c2), pick16(y2[i], c3), nib);
-        const uint32_t other = (uint32_t)__shfl_xor((int)nib, 1, 64);
-        if (active) {
-            const int64_t row = row0 + i;
-            *reinterpret_cast<uint32_t*>(vals + row * (F / 4) + (int64_t)blk * 2) = v;
-            if ((lane & 1) == 0) meta[row * (F / 16) + (blk >> 1)] = (uint8_t)(nib | (other << 4));
-        }
-    }
 }
 
 // eq. (6) evaluated only where y2 was kept.  One thread per (row, column block).
@@ -217,14 +133,6 @@ __global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* __r
             *reinterpret_cast<uint4*>(out_same + blk_off(r0 + rr, c0 + cs, C / 32)) = make_uint4(p[0], p[1], p[2], p[3]);
         }
     }
-}
-
-hipError_t launch_sqrelu_vnm_compress(const uint16_t* y1, int64_t T, int64_t F, uint16_t* vals, uint8_t* meta, uint8_t* colidx,
-                                      hipStream_t s) {
-    const int nblk = (int)(F / 8);
-    dim3 grid((unsigned)((nblk + 63) / 64), (unsigned)(T / 64));
-    hipLaunchKernelGGL(sqrelu_vnm_compress_kernel, grid, dim3(256), 0, s, y1, F, nblk, vals, meta, colidx);
-    return hipGetLastError();
 }
 
 hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uint8_t* meta, const uint8_t* colidx, int64_t T,

@@ -166,7 +166,8 @@ __global__ void __launch_bounds__(256) vnm_expand_t_m_kernel(const uint16_t* __r
 hipError_t launch_sqrelu_vnm_compress_m(const uint16_t* y1, int64_t T, int64_t F, int M, uint16_t* vals, uint8_t* meta, uint8_t* colidx,
                                         hipStream_t s) {
     dim3 grid((unsigned)((F + 255) / 256), (unsigned)(T / 64));
-    if (M == 16)      hipLaunchKernelGGL((sqrelu_vnm_compress_m_kernel<16>), grid, dim3(256), 0, s, y1, F, vals, meta, colidx);
+    if (M == 8)       hipLaunchKernelGGL((sqrelu_vnm_compress_m_kernel<8>), grid, dim3(256), 0, s, y1, F, vals, meta, colidx);
+    else if (M == 16) hipLaunchKernelGGL((sqrelu_vnm_compress_m_kernel<16>), grid, dim3(256), 0, s, y1, F, vals, meta, colidx);
     else if (M == 32) hipLaunchKernelGGL((sqrelu_vnm_compress_m_kernel<32>), grid, dim3(256), 0, s, y1, F, vals, meta, colidx);
     else if (M == 64) hipLaunchKernelGGL((sqrelu_vnm_compress_m_kernel<64>), grid, dim3(256), 0, s, y1, F, vals, meta, colidx);
     else return hipErrorInvalidValue;
