@@ -173,7 +173,8 @@ int venom_expert_matmul(const sffn_cfg* cfg, const int64_t* seg_offsets, const u
  * both weight gradients (eqs. (5), (8)); every contraction is grouped by expert, so all six shrink with 4/M.  Y3, dX [T,D]
  * come back in token order; dW1 [F,D], dW2 [D,F] are fully overwritten (hidden units of an expert without tokens: zeros).
  * Intermediates land in `workspace` at the offsets of sffn_router_workspace_layout() (row order of perm, rows =
- * sffn_venom_rows(T, M)).  Needs 4F/M a multiple of 64. */
+ * sffn_venom_rows(T, M)); dy2c is stored only with SFFN_FLAG_KEEP_DENSE (eq. (6) runs in the epilogue of eq. (4)).
+ * Needs 4F/M a multiple of 64. */
 typedef struct {
     size_t y1c, vals, meta, colidx, dy2c, dvals, total;   /* y1c, dy2c [rows,4F/M] bf16; vals, dvals [rows,2F/M]; meta [rows,F/(2M)] */
 } sffn_router_layout;

@@ -355,9 +355,10 @@ def moe_to_venom(X, W1, b1, means, M, mode=MODE_HARD):
 class FfnRouterStep:
     """ffn_router_step with a workspace allocated once (shapes and the routing's row capacity are fixed by T, D, F, M)."""
 
-    def __init__(self, T, D, F, M, mode=MODE_HARD, device="cuda"):
+    def __init__(self, T, D, F, M, mode=MODE_HARD, device="cuda", keep_dense=False):
+        """keep_dense: also store dy2c (SFFN_FLAG_KEEP_DENSE); eq. (6) is evaluated in the epilogue of eq. (4) either way."""
         self.T, self.D, self.F, self.M, self.mode = T, D, F, M, mode
-        self.cfg = _cfg(T, D, F, mode, M=M)
+        self.cfg = _cfg(T, D, F, mode, M=M, flags=FLAG_KEEP_DENSE if keep_dense else 0)
         lay = _RouterLayout()
         _check(load().sffn_router_workspace_layout(ctypes.byref(self.cfg), ctypes.byref(lay)))
         self.layout = {n: getattr(lay, n) for n, _ in _RouterLayout._fields_}

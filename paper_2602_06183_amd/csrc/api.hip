@@ -437,13 +437,13 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
     // would scatter 8-byte pieces M hidden units apart
     STAGE(launch_gemm_nt(0, at, nullptr, dypt, nullptr, Kc, D, rows, 0, wcb, D, s, &g2), "router/dW2.T");                 // eq. (5)
     STAGE(launch_transpose(wcb, F, D, D, dW2, 0, nullptr, s), "router/dW2");
-    {
+    {   // eq. (4) at the expert's hidden units, then eq. (6) on y2's slots while the tile is in LDS; dy2c itself only on request
         GemmGroup g4 = g1;
         g4.bias_stride = 0;
-        const VnmEpilogue plain;
-        STAGE(launch_gemm_vnm_epilogue(w2cvb, w2cmb, dyb, nullptr, Kc, rows, D, dy2c, plain, s, &g4), "router/dy2c");      // eq. (4) at the expert's columns
+        VnmEpilogue ep;
+        ep.mode = 4; ep.store_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0; ep.vals = dvals; ep.meta = meta; ep.ykept = y1c; ep.v24 = avb;
+        STAGE(launch_gemm_vnm_epilogue(w2cvb, w2cmb, dyb, nullptr, Kc, rows, D, dy2c, ep, s, &g4), "router/dy2c+dsqrelu");
     }
-    if (used > 0) STAGE(launch_venom_dsqrelu_compact(dy2c, y1c, meta, used, Kc, dvals, avb, s), "router/dsqrelu");          // eq. (6)
     STAGE(launch_transpose(W1, Kc, D, D, wcb, 1, nullptr, s, E, M), "router/W1[e].T");
     STAGE(launch_spmm_blocked(avb, amb, wcb, nullptr, rows, D, Kc, 0, dX, D, s, &g0), "router/dX");                       // eq. (7)
     STAGE(launch_venom_expand_t_compact(dvals, meta, rows, Kc, at, s), "router/expand(dy1)");

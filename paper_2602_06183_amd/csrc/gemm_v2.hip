@@ -384,6 +384,34 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                     }
                 }
             }
+            if (EPI == 4) {
+                // eq. (6) on the compact tile: lane = (token, group of four compact columns); the two kept positions come from the
+                // forward pass's metadata, y1 from the stored compact y1c (ep.ykept); dy2 is the bf16-rounded tile in LDS
+                const int g = lane & 15;
+                uint2 yv[16];
+                uint32_t mb[16];
+#pragma unroll
+                for (int it = 0; it < 16; ++it) {
+                    const int t = (lane >> 4) + 4 * it;
+                    const bool ok = valid && t0 + t < Rb;
+                    yv[it] = ok ? *reinterpret_cast<const uint2*>(ep.ykept + (int64_t)(t0 + t) * F + f0 + 4 * g) : make_uint2(0u, 0u);
+                    mb[it] = ok ? ep.meta[(int64_t)(t0 + t) * (F / 8) + (f0 >> 3) + (g >> 1)] : 0x44u;
+                }
+#pragma unroll
+                for (int it = 0; it < 16; ++it) {
+                    const int t = (lane >> 4) + 4 * it;
+                    const uint2 w = *reinterpret_cast<const uint2*>(scratch + t * EP + g * 8);
+                    const uint32_t nib = (mb[it] >> (4 * (g & 1))) & 0xFu, p0 = nib & 3u, p1 = nib >> 2;
+                    const uint32_t d0 = ((p0 >> 1) ? w.y : w.x) >> (16 * (p0 & 1)), d1 = ((p1 >> 1) ? w.y : w.x) >> (16 * (p1 & 1));
+                    const uint32_t y0 = ((p0 >> 1) ? yv[it].y : yv[it].x) >> (16 * (p0 & 1)), y1 = ((p1 >> 1) ? yv[it].y : yv[it].x) >> (16 * (p1 & 1));
+                    const float ya = bf2f(y0 & 0xFFFFu), yb = bf2f(y1 & 0xFFFFu);
+                    const uint32_t v = f2bf2(2.0f * bf2f(d0 & 0xFFFFu) * (ya > 0.0f ? ya : 0.0f), 2.0f * bf2f(d1 & 0xFFFFu) * (yb > 0.0f ? yb : 0.0f));
+                    if (valid && t0 + t < Rb) {
+                        *reinterpret_cast<uint32_t*>(ep.vals + (int64_t)(t0 + t) * (F / 2) + (f0 >> 1) + 2 * g) = v;
+                        *reinterpret_cast<uint32_t*>(ep.v24 + blk_off(t0 + t, (f0 >> 1) + 2 * g, F / 64)) = v;
+                    }
+                }
+            }
             if (EPI == 1 || EPI == 2) {
                 const int bl = lane & 7;                                  // column block handled in the per-row pass
                 const int64_t blk_g = (f0 >> 3) + bl;
@@ -571,6 +599,9 @@ hipError_t launch_gemm_vnm_epilogue(const uint16_t* a_vals, const uint8_t* a_met
     dim3 grid(tiles);
     if (ep.mode == 0)       // no V:N:M work: the dense output only
         hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 0, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
+                           tiles_m, tiles_n, ep, g);
+    else if (ep.mode == 4)
+        hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 4, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
                            tiles_m, tiles_n, ep, g);
     else if (ep.mode == 3)
         hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 3, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,

@@ -27,6 +27,8 @@ struct VnmEpilogue {
     // mode 3 (Section 3.3, neuron-level experts; grouped launch, A = one expert's hidden units in compact-column order):
     //        the tile of y1c gets the bias of its hidden units, is squared-ReLU'd and 2:4-pruned on every four consecutive
     //        compact columns: outputs vals, meta; padding rows (perm < 0) come out as zeros; `out` = y1c [rows, F] if store_dense.
+    // mode 4 (the same experts, backward): the tile of dy2c meets (meta, ykept = the stored y1c [rows, F]) and becomes dy1 in y2's
+    //        slots: outputs vals (canonical) and v24 (the same, blocked); `out` = dy2c if store_dense.
     const int32_t* perm = nullptr;
     int logM = 3;
 };
@@ -113,8 +115,6 @@ hipError_t launch_venom_route(const uint16_t* X, const uint16_t* means, int64_t 
 hipError_t launch_venom_permute(const int32_t* expert, int64_t T, int E, int64_t cap, int32_t* blockcnt, int32_t* seg, int32_t* perm,
                                 int32_t* row_of_token, hipStream_t s);
 hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, hipStream_t s);
-hipError_t launch_venom_dsqrelu_compact(const uint16_t* dy2c, const uint16_t* y1c, const uint8_t* meta, int64_t rows, int64_t Kc,
-                                        uint16_t* dvals, uint16_t* dvals_blk, hipStream_t s);
 hipError_t launch_venom_expand_t_compact(const uint16_t* vals, const uint8_t* meta, int64_t rows, int64_t Kc, uint16_t* at, hipStream_t s);
 hipError_t launch_fill_bytes(void* p, uint8_t v, size_t n_bytes, hipStream_t s);
 hipError_t launch_venom_colidx(const GemmGroup& g, int64_t cap, int64_t groups, uint8_t* colidx, hipStream_t s);

@@ -147,40 +147,6 @@ __global__ void __launch_bounds__(256) venom_gather_x_kernel(const uint16_t* __r
     *reinterpret_cast<uint4*>(xb + blk_off(r, c * 8, D >> 5)) = v;
 }
 
-// eq. (6) on the compact arrays of the router's output: slot s of group g of row r sits at compact column 4 g + p_s
-// (p_s from the metadata nibble); dvals = bf16(2 * dy2c * max(y1c, 0)) there.  One thread per metadata byte (two groups).
-__global__ void __launch_bounds__(256) venom_dsqrelu_compact_kernel(const uint16_t* __restrict__ dy2c, const uint16_t* __restrict__ y1c,
-                                                                   const uint8_t* __restrict__ meta, int64_t n_bytes, int Kc,
-                                                                   uint16_t* __restrict__ dvals, uint16_t* __restrict__ dvals_blk) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= n_bytes) return;
-    const uint4 dv = *reinterpret_cast<const uint4*>(dy2c + idx * 8);
-    const uint4 yv = *reinterpret_cast<const uint4*>(y1c + idx * 8);
-    const uint32_t mb = meta[idx];
-    const uint32_t dw[4] = {dv.x, dv.y, dv.z, dv.w}, yw[4] = {yv.x, yv.y, yv.z, yv.w};
-    uint32_t o[2];
-#pragma unroll
-    for (int g = 0; g < 2; ++g) {
-        const uint32_t nib = (mb >> (4 * g)) & 0xFu;
-        uint32_t r[2];
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const uint32_t p = (nib >> (2 * s)) & 3u;                       // position inside the group of four
-            const uint32_t d16 = (dw[2 * g + (p >> 1)] >> (16 * (p & 1))) & 0xFFFFu;
-            const uint32_t y16 = (yw[2 * g + (p >> 1)] >> (16 * (p & 1))) & 0xFFFFu;
-            const float y = bf2f(y16);
-            r[s] = f2bf(2.0f * bf2f(d16) * (y > 0.0f ? y : 0.0f));
-        }
-        o[g] = r[0] | (r[1] << 16);
-    }
-    *reinterpret_cast<uint2*>(dvals + idx * 4) = make_uint2(o[0], o[1]);
-    if (dvals_blk) {        // blocked operand layout of the packed [rows, Kc / 2] matrix
-        const int64_t r = idx / (Kc >> 3);
-        const int kk = (int)(idx - r * (Kc >> 3)) * 4;
-        *reinterpret_cast<uint2*>(dvals_blk + blk_off(r, kk, Kc >> 6)) = make_uint2(o[0], o[1]);
-    }
-}
-
 // (vals [rows, Kc / 2], meta [rows, Kc / 8]) -> the dense transposed matrix at[j, r] ([Kc, rows], row-major), zeros at the
 // dropped positions: the A operand of the weight-gradient contractions over each expert's run.  64 x 64 tiles through LDS.
 __global__ void __launch_bounds__(256) venom_expand_t_compact_kernel(const uint16_t* __restrict__ vals, const uint8_t* __restrict__ meta,
@@ -264,13 +230,6 @@ hipError_t launch_venom_permute(const int32_t* expert, int64_t T, int E, int64_t
 hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, hipStream_t s) {
     const int64_t n = cap * (D / 8);
     hipLaunchKernelGGL(venom_gather_x_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, X, perm, (int)cap, (int)D, xb);
-    return hipGetLastError();
-}
-
-hipError_t launch_venom_dsqrelu_compact(const uint16_t* dy2c, const uint16_t* y1c, const uint8_t* meta, int64_t rows, int64_t Kc,
-                                        uint16_t* dvals, uint16_t* dvals_blk, hipStream_t s) {
-    const int64_t n = rows * (Kc / 8);
-    hipLaunchKernelGGL(venom_dsqrelu_compact_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dy2c, y1c, meta, n, (int)Kc, dvals, dvals_blk);
     return hipGetLastError();
 }
 

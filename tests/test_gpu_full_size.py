@@ -249,10 +249,14 @@ def test_full_size_router_step(M):
     inp = make_router_inputs(T, D, F, M, seed=0)
     dev = {k: to_dev(v) for k, v in inp.items()}
     route = sffn.venom_route(dev["X"], dev["means"], M)
-    step = sffn.FfnRouterStep(T, D, F, M)
+    fast = sffn.FfnRouterStep(T, D, F, M)                           # the timed configuration
+    outs_fast = [to_bits(t).copy() for t in fast(route, dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    del fast
+    step = sffn.FfnRouterStep(T, D, F, M, keep_dense=True)
     outs = step(route, dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
     torch.cuda.synchronize()
     Y3, dX, dW1, dW2 = (to_bits(t) for t in outs)
+    assert all(np.array_equal(a, b) for a, b in zip(outs_fast, (Y3, dX, dW1, dW2)))
     sv = {k: to_bits(v) for k, v in step.saved().items()}
     expert = oracle.route_top1(oracle.route_scores(inp["X"], inp["means"]))
     perm, seg = oracle.expert_permutation(expert, M // 4)

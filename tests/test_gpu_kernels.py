@@ -480,11 +480,15 @@ def test_ffn_router_step_against_oracle(M, mode, T, D, F):
     inp = make_router_inputs(T, D, F, M, seed=3 * M + T, zero_fraction=0.75)
     dev = {k: to_dev(v) for k, v in inp.items()}
     route = sffn.venom_route(dev["X"], dev["means"], M)
-    step = sffn.FfnRouterStep(T, D, F, M, mode)
+    fast = sffn.FfnRouterStep(T, D, F, M, mode)                     # what bench.py --router times: dy2c never reaches HBM
+    outs_fast = [to_bits(t).copy() for t in fast(route, dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    dv_fast = to_bits(fast.saved()["dvals"]).copy()
+    step = sffn.FfnRouterStep(T, D, F, M, mode, keep_dense=True)
     outs = step(route, dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
     torch.cuda.synchronize()
     Y3, dX, dW1, dW2 = (to_bits(t) for t in outs)
     sv = {k: to_bits(v) for k, v in step.saved().items()}
+    assert all(np.array_equal(a, b) for a, b in zip(outs_fast, (Y3, dX, dW1, dW2))) and np.array_equal(dv_fast, sv["dvals"])
     expert = oracle.route_top1(oracle.route_scores(inp["X"], inp["means"]))
     perm, seg = oracle.expert_permutation(expert, M // 4)
     assert np.array_equal(to_bits(route["perm"]), perm) and route["seg"] == [int(v) for v in seg]
