@@ -514,3 +514,26 @@ def test_ffn_router_step_against_oracle(M, mode, T, D, F):
     assert_gemm_close(dX, oracle.vnm_spmm(dv, om, oc, inp["W1"], 1, 64, M)[rot], "dX")
     assert_gemm_close(dW2, oracle.vnm_wgrad(ov, om, oc, dyp, 0, 64, M), "dW2")
     assert_gemm_close(dW1, oracle.vnm_wgrad(dv, om, oc, xp, 1, 64, M), "dW1")
+
+
+def test_ffn_router_step_with_empty_experts():
+    """All tokens choose expert 2 of 4: the other experts' runs are empty, their hidden units get exact zero weight
+    gradients, and the step's outputs still match the oracle's contractions."""
+    M, T, D, F = 16, 130, 64, 512
+    inp = make_router_inputs(T, D, F, M, seed=4, zero_fraction=0.5)
+    inp["X"] = bf16_bits_from_f32(np.abs(oracle.bits_to_f32(inp["X"])))
+    inp["means"] = bf16_bits_from_f32(np.tile(np.array([[0.01], [0.02], [0.125], [-1.0]], dtype=np.float32), (1, D)))
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    route = sffn.venom_route(dev["X"], dev["means"], M)
+    assert route["seg"] == [0, 0, 0, 192, 192]
+    step = sffn.FfnRouterStep(T, D, F, M, keep_dense=True)
+    Y3, dX, dW1, dW2 = (to_bits(t) for t in step(route, dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"]))
+    ref = oracle.ffn_router_step_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"], inp["means"], M)
+    sv = {k: to_bits(v) for k, v in step.saved().items()}
+    assert np.array_equal(sv["colidx"], ref["colidx"]) and np.array_equal(sv["meta"][:192], ref["meta"][:192])     # same masks on this input
+    for got, key in ((Y3, "y3"), (dX, "dX"), (dW1, "dW1"), (dW2, "dW2")):
+        assert_gemm_close(got, ref[key], key)
+    for e in (0, 1, 3):
+        f = oracle.cluster_rows(e, M, F)
+        assert not dW1[f].any() and not dW2[:, f].any()
+    assert dW1[oracle.cluster_rows(2, M, F)].any()
