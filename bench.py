@@ -58,7 +58,7 @@ def main():
     ap.add_argument("--M", type=int, default=8, choices=[8, 16, 32, 64],
                     help="V:2:M block width of the activation format (Table 5); 8 is the headline configuration, wider blocks run the unfused path")
     ap.add_argument("--router", action="store_true",
-                    help="time the neuron-level router's training step (Section 3.3: venom_route + ffn_router_step, M / 4 experts) instead of the magnitude-based V:N:M step")
+                    help="time the neuron-level router's training step (Section 3.3: ffn_router_full_step = routing + grouped step, M / 4 experts) instead of the magnitude-based V:N:M step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference kernel for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -138,8 +138,8 @@ def main():
             dense_ffn(X, W1, W2, b1h, dY, y1, y2, y3, dy2, dy1, dXd, dW1d, dW2d)
 
     if args.router:
-        def sparse_step():          # Alg. 3 steps 1-2 (with the read-back of the run offsets), then the grouped step
-            step(sffn.venom_route(X, means, M), X, W1, W2, b1, dY)
+        def sparse_step():          # Alg. 3 steps 1-2 and the grouped step in one call; the run offsets stay on the device
+            step.full(means, X, W1, W2, b1, dY)
     else:
         def sparse_step():
             step(X, W1, W2, b1, dY)

@@ -184,6 +184,15 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
                     const uint16_t* W1, const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3,
                     uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
 
+/* venom_route + ffn_router_step in one call without a read-back: the run offsets stay on the device (they are written and
+ * read by this library's own kernels on `stream`), the grouped launches are sized for the worst case.  means as in
+ * venom_route; the step's intermediates sit at the offsets of sffn_router_workspace_layout(), the routing buffers behind
+ * them.  Same results as the two-call form. */
+size_t sffn_router_full_workspace_bytes(const sffn_cfg* cfg);
+int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint16_t* X, const uint16_t* W1,
+                         const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX,
+                         uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
+
 /* Alg. 1 + Alg. 2, one call: X [T,D], W1 [F,D], W2 [D,F], b1 fp32 [F] or NULL, dY [T,D] ->
  * Y3 [T,D], dX [T,D], dW1 [F,D], dW2 [D,F]; intermediates land in `workspace` at the offsets of
  * sffn_workspace_layout().  Both weight matrices are re-pruned inside the call.

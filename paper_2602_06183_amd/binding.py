@@ -79,6 +79,9 @@ def load():
     lib.sffn_router_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg)]
     lib.sffn_router_workspace_layout.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_RouterLayout)]
     lib.ffn_router_step.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(ctypes.c_int64)] + [p] * 10 + [p, sz, p]
+    lib.sffn_router_full_workspace_bytes.restype = sz
+    lib.sffn_router_full_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg)]
+    lib.ffn_router_full_step.argtypes = [ctypes.POINTER(_Cfg)] + [p] * 10 + [p, sz, p]
     lib.sffn_profile_enable.argtypes = [i32]
     lib.sffn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_char_p), i32]
     _LIB = lib
@@ -363,7 +366,8 @@ class FfnRouterStep:
         _check(load().sffn_router_workspace_layout(ctypes.byref(self.cfg), ctypes.byref(lay)))
         self.layout = {n: getattr(lay, n) for n, _ in _RouterLayout._fields_}
         self.rows = load().sffn_venom_rows(T, M)
-        self.ws = _u8((self.layout["total"],), device)
+        self.ws_bytes = load().sffn_router_full_workspace_bytes(ctypes.byref(self.cfg))    # step workspace + routing buffers
+        self.ws = _u8((self.ws_bytes,), device)
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
         self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
 
@@ -374,6 +378,12 @@ class FfnRouterStep:
         _check(load().ffn_router_step(ctypes.byref(self.cfg), seg_arr, _ptr(route["perm"]), _ptr(X), _ptr(W1),
                                       _ptr(W2), _ptr(b1), _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2),
                                       _ptr(self.ws), self.layout["total"], _stream()))
+        return self.Y3, self.dX, self.dW1, self.dW2
+
+    def full(self, means, X, W1, W2, b1, dY):
+        """Routing included (ffn_router_full_step): no read-back of the run offsets, nothing but launches on the stream."""
+        _check(load().ffn_router_full_step(ctypes.byref(self.cfg), _ptr(means), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY),
+                                           _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.ws_bytes, _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
 
     def saved(self):

@@ -360,10 +360,12 @@ int sffn_router_workspace_layout(const sffn_cfg* cfg, sffn_router_layout* out) {
     return SFFN_OK;
 }
 
-int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* X,
-                    const uint16_t* W1, const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
-                    uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
-    REQUIRE(cfg && seg_offsets && perm && X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_router_step: null pointer");
+// The router's training step.  The run offsets come either as a host array (validated here, passed to the kernels by value)
+// or as a device array written earlier on the same stream by this library's own grouping kernels (seg_dev).
+static int run_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* seg_dev, const int32_t* perm, const uint16_t* X,
+                           const uint16_t* W1, const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX,
+                           uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
+    REQUIRE(cfg && (seg_offsets || seg_dev) && perm && X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_router_step: null pointer");
     REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "ffn_router_step: only V=64 with M in {8, 16, 32, 64} is built");
     RouterLayout L;
     REQUIRE(make_router_layout(cfg, &L), SFFN_EINVAL, "ffn_router_step: T > 0, D and F positive multiples of 64, 4F/M a multiple of 64");
@@ -379,10 +381,14 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
     REQUIRE(workspace && ws_bytes >= L.total, SFFN_EWORKSPACE, "ffn_router_step: workspace missing or too small");
     GemmGroup g1;                                       // experts = weight operands, token runs = segments along j
     g1.n = E; g1.role = 1;
-    REQUIRE(seg_offsets[0] == 0 && seg_offsets[E] <= rows, SFFN_EINVAL, "ffn_router_step: seg_offsets must start at 0 and end within the row capacity");
-    for (int e = 0; e < E; ++e)
-        REQUIRE(seg_offsets[e + 1] >= seg_offsets[e] && seg_offsets[e + 1] % 64 == 0, SFFN_EINVAL, "ffn_router_step: seg_offsets must be ascending multiples of 64");
-    for (int e = 0; e <= E; ++e) g1.seg[e] = (int32_t)seg_offsets[e];
+    if (seg_dev) {
+        g1.seg_dev = seg_dev; g1.cap_rows = rows;
+    } else {
+        REQUIRE(seg_offsets[0] == 0 && seg_offsets[E] <= rows, SFFN_EINVAL, "ffn_router_step: seg_offsets must start at 0 and end within the row capacity");
+        for (int e = 0; e < E; ++e)
+            REQUIRE(seg_offsets[e + 1] >= seg_offsets[e] && seg_offsets[e + 1] % 64 == 0, SFFN_EINVAL, "ffn_router_step: seg_offsets must be ascending multiples of 64");
+        for (int e = 0; e <= E; ++e) g1.seg[e] = (int32_t)seg_offsets[e];
+    }
     g1.a_stride = Kc * D / 2; g1.m_stride = Kc * D / 8; g1.bias_stride = 4;
     GemmGroup g0 = g1;                                  // eqs. (3), (7): token runs along i, the expert's [D, Kc] weight slice as B
     g0.role = 0; g0.a_stride = g0.m_stride = g0.bias_stride = 0; g0.b_stride = D * Kc;
@@ -391,7 +397,7 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
     g2.role = 2; g2.a_stride = g2.m_stride = g2.bias_stride = 0; g2.out_stride = 0;
     const int logM = M == 8 ? 3 : M == 16 ? 4 : M == 32 ? 5 : 6;
     g2.map_logM = logM;
-    const int64_t used = seg_offsets[E];
+    const int64_t used = seg_dev ? 0 : seg_offsets[E];   // (device table: the end of the last run is only known on the device)
 
     hipStream_t s = (hipStream_t)stream;
     unsigned char* ws = (unsigned char*)workspace;
@@ -410,7 +416,14 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
     STAGE(launch_transpose(X, rows, D, D, xpt, 0, xb, s, 1, 0, perm), "router/X[perm].T");     // permuted rows: transposed (eq. (8)) and blocked (eq. (1))
     STAGE(launch_prune24_step(W1, F, D, D, 0, cfg->mode, w1cv, w1cm, w1cvb, w1cmb, nullptr, s, 1, M), "router/prune24(W1)");
     STAGE(launch_venom_colidx(g1, rows, F / M, colidx, s), "router/colidx");
-    if (used < rows) {      // rows past the last run are padding that no contraction writes
+    if (seg_dev) {          // rows past the last run are padding that no contraction writes; at most 64 (E + 1) of them
+        const int64_t mt = 64 * (E + 1);
+        LAUNCH(launch_fill_tail_rows(vals, 0, seg_dev + E, rows, Kc, mt, s), "router/clear");
+        LAUNCH(launch_fill_tail_rows(meta, 0x44, seg_dev + E, rows, Kc / 8, mt, s), "router/clear");
+        LAUNCH(launch_fill_tail_rows(y1c, 0, seg_dev + E, rows, Kc * 2, mt, s), "router/clear");
+        LAUNCH(launch_fill_tail_rows(dy2c, 0, seg_dev + E, rows, Kc * 2, mt, s), "router/clear");
+        LAUNCH(launch_fill_tail_rows(dvals, 0, seg_dev + E, rows, Kc, mt, s), "router/clear");
+    } else if (used < rows) {
         const int64_t tail = rows - used;
         LAUNCH(launch_fill_bytes(vals + used * (Kc / 2), 0, (size_t)tail * Kc, s), "router/clear");
         LAUNCH(launch_fill_bytes(meta + used * (Kc / 8), 0x44, (size_t)tail * (Kc / 8), s), "router/clear");
@@ -449,6 +462,58 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
     STAGE(launch_venom_expand_t_compact(dvals, meta, rows, Kc, at, s), "router/expand(dy1)");
     STAGE(launch_gemm_nt(0, at, nullptr, xpt, nullptr, Kc, D, rows, 0, dW1, D, s, &g2), "router/dW1");                    // eq. (8)
     return SFFN_OK;
+}
+
+int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* X,
+                    const uint16_t* W1, const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
+                    uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
+    REQUIRE(seg_offsets, SFFN_EINVAL, "ffn_router_step: null pointer");
+    return run_router_step(cfg, seg_offsets, nullptr, perm, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, ws_bytes, stream);
+}
+
+// Routing buffers of ffn_router_full_step, behind the step's own workspace: expert [T], perm [rows], row_of_token [T],
+// seg [E + 1], per-block counts.
+namespace {
+struct RouteArea { size_t expert, perm, row_of_token, seg, counts, total; };
+bool make_route_area(const sffn_cfg* c, size_t base, RouteArea* A) {
+    if (!c || c->T <= 0 || !vnm_ok(c->V, c->M)) return false;
+    const size_t T = c->T, rows = (size_t)sffn_venom_rows(c->T, c->M);
+    size_t off = base;
+    auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
+    A->expert = take(T * 4); A->perm = take(rows * 4); A->row_of_token = take(T * 4); A->seg = take(68 * 4);
+    A->counts = take(sffn_venom_route_workspace_bytes(c->T, c->M));
+    A->total = off;
+    return true;
+}
+}  // namespace
+
+size_t sffn_router_full_workspace_bytes(const sffn_cfg* cfg) {
+    RouterLayout L;
+    RouteArea A;
+    if (!make_router_layout(cfg, &L) || !make_route_area(cfg, L.total, &A)) return 0;
+    return A.total;
+}
+
+int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint16_t* X, const uint16_t* W1, const uint16_t* W2,
+                         const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace,
+                         size_t ws_bytes, void* stream) {
+    REQUIRE(cfg && means && X && workspace, SFFN_EINVAL, "ffn_router_full_step: null pointer");
+    REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "ffn_router_full_step: only V=64 with M in {8, 16, 32, 64} is built");
+    RouterLayout L;
+    RouteArea A;
+    REQUIRE(make_router_layout(cfg, &L) && make_route_area(cfg, L.total, &A), SFFN_EINVAL,
+            "ffn_router_full_step: T > 0, D and F positive multiples of 64, 4F/M a multiple of 64");
+    REQUIRE(aligned16(workspace) && aligned16(means), SFFN_EINVAL, "ffn_router_full_step: pointers must be 16-byte aligned");
+    REQUIRE(ws_bytes >= A.total, SFFN_EWORKSPACE, "ffn_router_full_step: workspace too small");
+    unsigned char* ws = (unsigned char*)workspace;
+    int32_t* expert = (int32_t*)(ws + A.expert);
+    int32_t* perm = (int32_t*)(ws + A.perm);
+    int32_t* seg = (int32_t*)(ws + A.seg);
+    const int rc = venom_route(X, means, cfg->T, cfg->D, cfg->M, expert, perm, (int32_t*)(ws + A.row_of_token), seg, nullptr, ws + A.counts,
+                               A.total - A.counts, stream);
+    if (rc != SFFN_OK) return rc;
+    // the run offsets stay on the device: no read-back, the grouped launches are sized for the worst case
+    return run_router_step(cfg, nullptr, seg, perm, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, L.total, stream);
 }
 
 // Alg. 1 + Alg. 2 for n_experts independent FFNs over consecutive token segments (n_experts = 1, seg = nullptr:

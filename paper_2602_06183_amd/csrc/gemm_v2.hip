@@ -61,7 +61,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     }
     // Grouped form: find the expert of this tile and narrow the problem to its token segment.
     const int Kld = K;                   // K extent of the stored operands (block-row stride)
-    const int tok_ld = grp.n ? grp.seg[grp.n] : Rb;       // tokens in the token-indexed outputs of the V:N:M epilogue
+#define SEG(i) (grp.seg_dev ? grp.seg_dev[i] : grp.seg[i])
+    const int tok_ld = grp.n ? SEG(grp.n) : Rb;       // tokens in the token-indexed outputs of the V:N:M epilogue
     int i_base = 0, j_base = 0;
     int expert_id = 0;
     if (!SPARSE && !BLOCKED && grp.n && grp.role == 2) {
@@ -70,8 +71,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         expert_id = L / per;
         L -= expert_id * per;
         if (expert_id >= grp.n) return;
-        const int k0 = grp.seg[expert_id];
-        K = grp.seg[expert_id + 1] - k0;
+        const int k0 = SEG(expert_id);
+        K = SEG(expert_id + 1) - k0;
         a_vals += k0; B += k0;
         out += expert_id * grp.out_stride;
     } else if (grp.n) {
@@ -80,13 +81,14 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
             const int other = grp.role == 0 ? tiles_n : tiles_m;
             int cnt = 0;
             for (; e < grp.n; ++e) {
-                cnt = ((grp.seg[e + 1] - grp.seg[e] + 255) >> 8) * other;
+                cnt = ((SEG(e + 1) - SEG(e) + 255) >> 8) * other;
                 if (L < cnt) break;
                 L -= cnt;
             }
             if (e == grp.n) return;      // (the launcher sizes the grid exactly; kept as a guard)
-            if (grp.role == 0) { tiles_m = cnt / other; i_base = grp.seg[e]; Ra = grp.seg[e + 1]; }
-            else               { tiles_n = cnt / other; j_base = grp.seg[e]; Rb = grp.seg[e + 1]; }
+            if (grp.role == 0) { tiles_m = cnt / other; i_base = SEG(e); Ra = SEG(e + 1); }
+            else               { tiles_n = cnt / other; j_base = SEG(e); Rb = SEG(e + 1); }
+#undef SEG
         }
         if (grp.role != 0) { a_vals += e * grp.a_stride; if (SPARSE) a_meta += e * grp.m_stride; }
         if (grp.role != 1) B += e * grp.b_stride;
@@ -549,6 +551,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
 static unsigned grid_tiles(int tiles_m, int tiles_n, const GemmGroup& g) {
     if (g.n == 0) return (unsigned)(tiles_m * tiles_n);
     if (g.role == 2) return (unsigned)(g.n * tiles_m * tiles_n);
+    if (g.seg_dev) return (unsigned)(((g.cap_rows + 255) / 256 + g.n) * (g.role == 0 ? tiles_n : tiles_m));   // worst case over all run lengths
     int tok_tiles = 0;
     for (int e = 0; e < g.n; ++e) tok_tiles += (g.seg[e + 1] - g.seg[e] + 255) / 256;
     return (unsigned)(tok_tiles * (g.role == 0 ? tiles_n : tiles_m));

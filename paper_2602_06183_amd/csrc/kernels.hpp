@@ -50,6 +50,11 @@ struct GemmGroup {
     int map_logM = 0;
     // roles 0 / none with the i-major output: row i goes to row out_row_map[i] of the output (negative: not stored)
     const int32_t* out_row_map = nullptr;
+    // Segment offsets kept on the device (written by an earlier kernel of the same call, e.g. the router's grouping): when set,
+    // the kernels read seg_dev[0..n] instead of seg[], and the launch is sized for the worst case of `cap_rows` token rows in n
+    // runs (workgroups past the real tile count exit at once).  gemm_v2.hip kernels and the router's helpers only.
+    const int32_t* seg_dev = nullptr;
+    int64_t cap_rows = 0;
     int32_t seg[kMaxExperts + 1] = {0};
 };
 
@@ -117,6 +122,8 @@ hipError_t launch_venom_permute(const int32_t* expert, int64_t T, int E, int64_t
 hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, hipStream_t s);
 hipError_t launch_venom_expand_t_compact(const uint16_t* vals, const uint8_t* meta, int64_t rows, int64_t Kc, uint16_t* at, hipStream_t s);
 hipError_t launch_fill_bytes(void* p, uint8_t v, size_t n_bytes, hipStream_t s);
+hipError_t launch_fill_tail_rows(void* p, uint8_t v, const int32_t* first_row, int64_t rows, int64_t row_bytes, int64_t max_tail_rows,
+                                 hipStream_t s);
 hipError_t launch_venom_colidx(const GemmGroup& g, int64_t cap, int64_t groups, uint8_t* colidx, hipStream_t s);
 
 hipError_t launch_wgrad_vnm(const uint16_t* atc, const uint8_t* kmask, const uint16_t* G, int64_t F, int64_t N, int64_t T,

@@ -185,13 +185,30 @@ __global__ void __launch_bounds__(256) venom_colidx_kernel(GemmGroup g, int nblo
     const int tb = (int)(idx / groups);
     int e = 0;
     for (int q = 0; q < g.n; ++q)
-        if (tb * 64 >= g.seg[q] && tb * 64 < g.seg[q + 1]) e = q;
+        if (tb * 64 >= (g.seg_dev ? g.seg_dev[q] : g.seg[q]) && tb * 64 < (g.seg_dev ? g.seg_dev[q + 1] : g.seg[q + 1])) e = q;
     colidx[idx] = 0x03020100u + 0x04040404u * (uint32_t)e;
 }
 
 __global__ void __launch_bounds__(256) fill_words_kernel(uint32_t* __restrict__ p, uint32_t v, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < n) p[i] = v;
+}
+
+// rows first_row[0] .. rows - 1 of a [rows, row_words] array <- v (first_row lives on the device: the end of the last run)
+__global__ void __launch_bounds__(256) fill_tail_rows_kernel(uint32_t* __restrict__ p, uint32_t v, const int32_t* __restrict__ first_row,
+                                                            int64_t rows, int64_t row_words) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x + (int64_t)first_row[0] * row_words;
+    if (i < rows * row_words) p[i] = v;
+}
+
+// worst case: the last 64 * n_runs rows (every run can add at most 63 rows of padding, the capacity leaves 64 per run)
+hipError_t launch_fill_tail_rows(void* p, uint8_t v, const int32_t* first_row, int64_t rows, int64_t row_bytes, int64_t max_tail_rows,
+                                 hipStream_t s) {
+    const int64_t n = max_tail_rows * (row_bytes / 4);
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_tail_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (uint32_t*)p, 0x01010101u * v, first_row, rows,
+                       row_bytes / 4);
+    return hipGetLastError();
 }
 
 // n_bytes (a multiple of 4) bytes at p <- byte value v; a kernel rather than a memset node, so that callers may capture it

@@ -121,6 +121,11 @@ def test_router_entry_points_validate_on_the_host():
     assert lib.ffn_router_step(ctypes.byref(bad), ok, *args, fake, big, None) == -1
     m12 = binding._Cfg(100, 64, 1024, 64, 12, 0, 0)
     assert lib.ffn_router_step(ctypes.byref(m12), ok, *args, fake, big, None) == -2
+    assert lib.sffn_router_full_workspace_bytes(ctypes.byref(cfg)) > lib.sffn_router_workspace_bytes(ctypes.byref(cfg))
+    assert lib.sffn_router_full_workspace_bytes(ctypes.byref(bad)) == 0
+    assert lib.ffn_router_full_step(ctypes.byref(cfg), *args, fake, 16, None) == -3
+    assert lib.ffn_router_full_step(ctypes.byref(cfg), None, *args[1:], fake, big, None) == -1
+    assert lib.ffn_router_full_step(ctypes.byref(m12), *args, fake, big, None) == -2
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

@@ -489,6 +489,12 @@ def test_ffn_router_step_against_oracle(M, mode, T, D, F):
     Y3, dX, dW1, dW2 = (to_bits(t) for t in outs)
     sv = {k: to_bits(v) for k, v in step.saved().items()}
     assert all(np.array_equal(a, b) for a, b in zip(outs_fast, (Y3, dX, dW1, dW2))) and np.array_equal(dv_fast, sv["dvals"])
+    # the one-call form (routing inside, run offsets never leave the device) must give the same bits
+    one = sffn.FfnRouterStep(T, D, F, M, mode)
+    outs_one = [to_bits(t) for t in one.full(dev["means"], dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    sv_one = {k: to_bits(v) for k, v in one.saved().items()}
+    assert all(np.array_equal(a, b) for a, b in zip(outs_one, (Y3, dX, dW1, dW2)))
+    assert all(np.array_equal(sv_one[k], sv[k]) for k in ("y1c", "vals", "meta", "colidx", "dvals"))
     expert = oracle.route_top1(oracle.route_scores(inp["X"], inp["means"]))
     perm, seg = oracle.expert_permutation(expert, M // 4)
     assert np.array_equal(to_bits(route["perm"]), perm) and route["seg"] == [int(v) for v in seg]
@@ -537,3 +543,6 @@ def test_ffn_router_step_with_empty_experts():
         f = oracle.cluster_rows(e, M, F)
         assert not dW1[f].any() and not dW2[:, f].any()
     assert dW1[oracle.cluster_rows(2, M, F)].any()
+    one = sffn.FfnRouterStep(T, D, F, M)
+    outs_one = [to_bits(t) for t in one.full(dev["means"], dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    assert all(np.array_equal(a, b) for a, b in zip(outs_one, (Y3, dX, dW1, dW2)))
