@@ -405,7 +405,8 @@ def test_ffn_sparse_step_wide_blocks(M, mode, F):
 
 # ---- neuron-level router (Section 3.3, Alg. 3) -------------------------------------------------------------------
 
-@pytest.mark.parametrize("T,D,M", [(300, 192, 8), (1500, 256, 16), (2100, 1024, 32), (4096, 520, 64), (64, 64, 16), (1, 2048, 8)])
+@pytest.mark.parametrize("T,D,M", [(300, 192, 8), (1500, 256, 16), (2100, 1024, 32), (4096, 520, 64), (64, 64, 16), (1, 2048, 8),
+                                   (70001, 64, 64)])
 def test_venom_route_matches_oracle_bit_for_bit(T, D, M):
     """Steps 1-2: float32 scores in the stated order (bit-exact, so the argmax is too), stable 64-row padded grouping."""
     inp = make_router_inputs(T, D, 256, M, seed=T + M)

@@ -194,3 +194,22 @@ def test_router_step_backward_is_the_gradient_of_its_forward():
     unused = [e for e in range(M // 4) if ref["seg"][e + 1] == ref["seg"][e]]
     for e in unused:
         assert not ref["dW1"][oracle.cluster_rows(e, M, F)].any() and not ref["dW2"][:, oracle.cluster_rows(e, M, F)].any()
+
+
+@pytest.mark.parametrize("M,F", [(8, 64), (16, 128), (32, 256), (64, 1024)])
+def test_cluster_rows_partition_the_hidden_units(M, F):
+    """The experts' hidden units are non-overlapping and cover all of them (Section 3.3: non-overlapping subsets), four
+    consecutive units of every M-block each, and scatter_compact puts compact column j of expert e exactly there."""
+    E = M // 4
+    allrows = np.concatenate([oracle.cluster_rows(e, M, F) for e in range(E)])
+    assert sorted(allrows) == list(range(F))
+    for e in range(E):
+        r = oracle.cluster_rows(e, M, F)
+        assert len(r) == 4 * F // M and np.all((r % M) // 4 == e) and np.all(np.diff(r.reshape(-1, 4), axis=1) == 1)
+    seg = np.arange(E + 1) * 64
+    c = (np.arange(64 * E * (4 * F // M)).reshape(64 * E, 4 * F // M) % 65000 + 1).astype(np.uint16)
+    full = oracle.scatter_compact(c, seg, M, F)
+    for e in range(E):
+        rows = slice(64 * e, 64 * e + 64)
+        assert np.array_equal(full[rows][:, oracle.cluster_rows(e, M, F)], c[rows])
+        assert np.count_nonzero(full[rows]) == c[rows].size
