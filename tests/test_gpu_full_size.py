@@ -240,18 +240,19 @@ def test_full_size_router(M):
         assert Kc == y1c.shape[1]
 
 
-@pytest.mark.parametrize("M", [16, 64])
-def test_full_size_router_step(M):
-    """ffn_router_step at the 1B shape as bench.py --router times it: routing bit-exact in full; packing and eq. (6)
+@pytest.mark.parametrize("name,M", [("1b", 16), ("1b", 64), ("7b", 16)])
+def test_full_size_router_step(name, M):
+    """ffn_router_step at the 1B and 7B shapes as bench.py --router times it: routing bit-exact in full; packing and eq. (6)
     bit-exact on sampled 64-row blocks from the GPU's own y1c / dy2c; every contraction on sampled rows / hidden units."""
     from workload import make_router_inputs
-    T, D, F = CONFIGS["1b"]
+    T, D, F = CONFIGS[name]
     inp = make_router_inputs(T, D, F, M, seed=0)
     dev = {k: to_dev(v) for k, v in inp.items()}
     route = sffn.venom_route(dev["X"], dev["means"], M)
-    fast = sffn.FfnRouterStep(T, D, F, M)                           # the timed configuration
-    outs_fast = [to_bits(t).copy() for t in fast(route, dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    fast = sffn.FfnRouterStep(T, D, F, M)                           # the timed configuration: routing inside, dy2c not stored
+    outs_fast = [to_bits(t).copy() for t in fast.full(dev["means"], dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
     del fast
+    torch.cuda.empty_cache()
     step = sffn.FfnRouterStep(T, D, F, M, keep_dense=True)
     outs = step(route, dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
     torch.cuda.synchronize()
