@@ -308,10 +308,10 @@ int venom_expert_matmul(const sffn_cfg* cfg, const int64_t* seg_offsets, const u
     LAUNCH(launch_venom_colidx(g, cap, F / M, colidx, s), "venom_expert_matmul/colidx");
     // rows past the last run are never touched by the grouped contraction: clear them (they are padding)
     if (seg_offsets[E] < cap) {
-        const int64_t rows = cap - seg_offsets[E];
-        LAUNCH(launch_fill_bytes(vals + seg_offsets[E] * (Kc / 2), 0, (size_t)rows * Kc, s), "venom_expert_matmul/clear");
-        LAUNCH(launch_fill_bytes(meta + seg_offsets[E] * (Kc / 8), 0x44, (size_t)rows * (Kc / 8), s), "venom_expert_matmul/clear");
-        if (y1c) LAUNCH(launch_fill_bytes(y1c + seg_offsets[E] * Kc, 0, (size_t)rows * Kc * 2, s), "venom_expert_matmul/clear");
+        TailFill tf;
+        tf.add(vals, Kc, 0); tf.add(meta, Kc / 8, 0x44);
+        if (y1c) tf.add(y1c, Kc * 2, 0);
+        LAUNCH(launch_fill_tail_rows(tf, nullptr, seg_offsets[E], cap, cap - seg_offsets[E], s), "venom_expert_matmul/clear");
     }
     VnmEpilogue ep;
     ep.mode = 3; ep.store_dense = y1c ? 1 : 0; ep.vals = vals; ep.meta = meta; ep.perm = perm;
@@ -416,20 +416,11 @@ static int run_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, cons
     STAGE(launch_transpose(X, rows, D, D, xpt, 0, xb, s, 1, 0, perm), "router/X[perm].T");     // permuted rows: transposed (eq. (8)) and blocked (eq. (1))
     STAGE(launch_prune24_step(W1, F, D, D, 0, cfg->mode, w1cv, w1cm, w1cvb, w1cmb, nullptr, s, 1, M), "router/prune24(W1)");
     STAGE(launch_venom_colidx(g1, rows, F / M, colidx, s), "router/colidx");
-    if (seg_dev) {          // rows past the last run are padding that no contraction writes; at most 64 (E + 1) of them
-        const int64_t mt = 64 * (E + 1);
-        LAUNCH(launch_fill_tail_rows(vals, 0, seg_dev + E, rows, Kc, mt, s), "router/clear");
-        LAUNCH(launch_fill_tail_rows(meta, 0x44, seg_dev + E, rows, Kc / 8, mt, s), "router/clear");
-        LAUNCH(launch_fill_tail_rows(y1c, 0, seg_dev + E, rows, Kc * 2, mt, s), "router/clear");
-        LAUNCH(launch_fill_tail_rows(dy2c, 0, seg_dev + E, rows, Kc * 2, mt, s), "router/clear");
-        LAUNCH(launch_fill_tail_rows(dvals, 0, seg_dev + E, rows, Kc, mt, s), "router/clear");
-    } else if (used < rows) {
-        const int64_t tail = rows - used;
-        LAUNCH(launch_fill_bytes(vals + used * (Kc / 2), 0, (size_t)tail * Kc, s), "router/clear");
-        LAUNCH(launch_fill_bytes(meta + used * (Kc / 8), 0x44, (size_t)tail * (Kc / 8), s), "router/clear");
-        LAUNCH(launch_fill_bytes(y1c + used * Kc, 0, (size_t)tail * Kc * 2, s), "router/clear");
-        LAUNCH(launch_fill_bytes(dy2c + used * Kc, 0, (size_t)tail * Kc * 2, s), "router/clear");
-        LAUNCH(launch_fill_bytes(dvals + used * (Kc / 2), 0, (size_t)tail * Kc, s), "router/clear");
+    {   // rows past the last run are padding that no contraction writes: one launch clears them in the five row-indexed outputs
+        TailFill tf;
+        tf.add(vals, Kc, 0); tf.add(meta, Kc / 8, 0x44); tf.add(y1c, Kc * 2, 0); tf.add(dy2c, Kc * 2, 0); tf.add(dvals, Kc, 0);
+        if (seg_dev) LAUNCH(launch_fill_tail_rows(tf, seg_dev + E, 0, rows, 64 * (E + 1), s), "router/clear");      // at most 64 (E + 1) such rows
+        else if (used < rows) LAUNCH(launch_fill_tail_rows(tf, nullptr, used, rows, rows - used, s), "router/clear");
     }
     // Inside a run every 64-row block keeps the same columns, so eqs. (3), (7) are plain grouped 2:4 contractions of the
     // packed [rows, Kc] activation with the expert's own [D, Kc] slice of W2 / W1.T (256 x 256 tiles; gathering rows per

@@ -121,8 +121,14 @@ hipError_t launch_venom_permute(const int32_t* expert, int64_t T, int E, int64_t
                                 int32_t* row_of_token, hipStream_t s);
 hipError_t launch_venom_gather_x(const uint16_t* X, const int32_t* perm, int64_t cap, int64_t D, uint16_t* xb, hipStream_t s);
 hipError_t launch_venom_expand_t_compact(const uint16_t* vals, const uint8_t* meta, int64_t rows, int64_t Kc, uint16_t* at, hipStream_t s);
-hipError_t launch_fill_bytes(void* p, uint8_t v, size_t n_bytes, hipStream_t s);
-hipError_t launch_fill_tail_rows(void* p, uint8_t v, const int32_t* first_row, int64_t rows, int64_t row_bytes, int64_t max_tail_rows,
+struct TailFill {                   // up to five arrays of `rows` rows whose tail rows get a fill word
+    int n = 0;
+    uint32_t* p[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    int64_t row_words[5] = {0, 0, 0, 0, 0};
+    uint32_t v[5] = {0, 0, 0, 0, 0};
+    void add(void* ptr, int64_t row_bytes, uint8_t byte) { p[n] = (uint32_t*)ptr; row_words[n] = row_bytes / 4; v[n] = 0x01010101u * byte; ++n; }
+};
+hipError_t launch_fill_tail_rows(const TailFill& f, const int32_t* first_dev, int64_t first_imm, int64_t rows, int64_t max_tail_rows,
                                  hipStream_t s);
 hipError_t launch_venom_colidx(const GemmGroup& g, int64_t cap, int64_t groups, uint8_t* colidx, hipStream_t s);
 

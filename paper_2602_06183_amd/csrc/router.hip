@@ -189,33 +189,22 @@ __global__ void __launch_bounds__(256) venom_colidx_kernel(GemmGroup g, int nblo
     colidx[idx] = 0x03020100u + 0x04040404u * (uint32_t)e;
 }
 
-__global__ void __launch_bounds__(256) fill_words_kernel(uint32_t* __restrict__ p, uint32_t v, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = v;
+// Padding rows past the last run: rows first .. rows - 1 of up to five [rows, row_words] arrays <- their fill words, in one
+// launch.  `first` comes from the device (first_dev[0], the end of the last run) or as an immediate.
+__global__ void __launch_bounds__(256) fill_tail_rows_kernel(TailFill f, const int32_t* __restrict__ first_dev, int first_imm, int64_t rows) {
+    const int a = blockIdx.y;
+    const int64_t first = first_dev ? first_dev[0] : first_imm;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x + first * f.row_words[a];
+    if (i < rows * f.row_words[a]) f.p[a][i] = f.v[a];
 }
 
-// rows first_row[0] .. rows - 1 of a [rows, row_words] array <- v (first_row lives on the device: the end of the last run)
-__global__ void __launch_bounds__(256) fill_tail_rows_kernel(uint32_t* __restrict__ p, uint32_t v, const int32_t* __restrict__ first_row,
-                                                            int64_t rows, int64_t row_words) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x + (int64_t)first_row[0] * row_words;
-    if (i < rows * row_words) p[i] = v;
-}
-
-// worst case: the last 64 * n_runs rows (every run can add at most 63 rows of padding, the capacity leaves 64 per run)
-hipError_t launch_fill_tail_rows(void* p, uint8_t v, const int32_t* first_row, int64_t rows, int64_t row_bytes, int64_t max_tail_rows,
+hipError_t launch_fill_tail_rows(const TailFill& f, const int32_t* first_dev, int64_t first_imm, int64_t rows, int64_t max_tail_rows,
                                  hipStream_t s) {
-    const int64_t n = max_tail_rows * (row_bytes / 4);
-    if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL(fill_tail_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (uint32_t*)p, 0x01010101u * v, first_row, rows,
-                       row_bytes / 4);
-    return hipGetLastError();
-}
-
-// n_bytes (a multiple of 4) bytes at p <- byte value v; a kernel rather than a memset node, so that callers may capture it
-hipError_t launch_fill_bytes(void* p, uint8_t v, size_t n_bytes, hipStream_t s) {
-    if (n_bytes == 0) return hipSuccess;
-    const int64_t n = (int64_t)(n_bytes / 4);
-    hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (uint32_t*)p, 0x01010101u * v, n);
+    int64_t widest = 0;
+    for (int a = 0; a < f.n; ++a) widest = f.row_words[a] > widest ? f.row_words[a] : widest;
+    const int64_t n = max_tail_rows * widest;
+    if (n == 0 || f.n == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_tail_rows_kernel, dim3((unsigned)((n + 255) / 256), (unsigned)f.n), dim3(256), 0, s, f, first_dev, (int)first_imm, rows);
     return hipGetLastError();
 }
 
