@@ -1,12 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the sparsified FFN training step (one pass of Alg. 1 + Alg. 2 = one "step") on one MI355X.
 
-Prints one JSON line: dense-equivalent TFLOP/s of ffn_sparse_step (12*T*D*F flop per step), the
-speed-up over a dense bf16 FFN step built from hipBLASLt GEMMs (torch.matmul) timed in the same
-process, a roofline record for the kernel that takes most of the step, and the CPU oracle timed
-on the host cores as a reported baseline.
+Prints ONE JSON line.  Headline (`value`, `ms_per_step`, `config.workload`, `roofline`, `cpu_baseline`): the largest
+single-GPU configuration, the 70B-scale layer (T = 8192, d_model = 8192, d_ff = 28672) at ReLU zero fraction 0.90:
+dense-equivalent TFLOP/s of ffn_sparse_step (12*T*D*F flop per step) and the speed-up over a dense bf16 FFN step built from
+hipBLASLt GEMMs (torch.matmul) plus one-pass element-wise kernels, timed in the same process.  Under `configs` the same
+figures for every other benchmark configuration (tiny, 1B, 7B, the 8-expert MoE layer, and the 70B layer at zero fractions
+0.50 / 0.75 / 0.95); under `standalone_kernels` the two compressors alone at the 7B shape (HBM-bound, buffers rotated so
+that no launch finds its input in the last-level cache); the 2:4 / V:N:M GEMM micro-benchmarks and the router's conversion
+cost at the 1B shape.  `--workload W` makes W the headline instead (used for profiling one configuration).
 """
 import argparse
+import gc
 import json
 import os
 import sys
@@ -17,6 +22,10 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
 HBM_PEAK_GBS = 8000.0
+SPARSE_GEMM = "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>"
+DENSE_GEMM = "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>"
+WGRAD = "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>"
+ROUTER_GEMMS = ("router/y1c+sqrelu+2:4", "router/dy2c+dsqrelu", "router/y3", "router/dX", "router/dW2.T", "router/dW1")
 
 
 def algorithmic_flops(stage, T, D, F, M=8):
@@ -24,7 +33,7 @@ def algorithmic_flops(stage, T, D, F, M=8):
     tdf = float(T) * D * F
     act = 4.0 / M * tdf                                          # V:2:M activations: 2 of M survive (M = 8: a quarter)
     if stage.startswith("router/"):                              # neuron-level experts: every contraction covers 4 / M of the hidden units
-        return act if stage in ("router/y1c+sqrelu+2:4", "router/dy2c", "router/y3", "router/dX", "router/dW2.T", "router/dW1") else None
+        return act if stage in ROUTER_GEMMS else None
     return {"step/y1+sqrelu_vnm_compress": tdf, "step/dy2+dsqrelu_vnm": tdf, "step/y1": tdf, "step/dy2": tdf,   # 2:4 weights: half of K survives
             "step/y3": act, "step/dX": act, "step/dW2": act, "step/dW1": act}.get(stage)
 
@@ -33,18 +42,15 @@ def executed_flops(stage, T, D, F, M=8):
     """Flops the matrix cores are issued for (dense-equivalent of the instructions used)."""
     tdf = float(T) * D * F
     if stage.startswith("router/"):
-        return 8.0 / M * tdf if stage in ("router/y1c+sqrelu+2:4", "router/dy2c", "router/y3", "router/dX", "router/dW2.T", "router/dW1") else None
+        return 8.0 / M * tdf if stage in ROUTER_GEMMS else None
     return {"step/y1+sqrelu_vnm_compress": 2 * tdf, "step/dy2+dsqrelu_vnm": 2 * tdf, "step/y1": 2 * tdf, "step/dy2": 2 * tdf,
             "step/y3": 2 * tdf, "step/dX": 2 * tdf, "step/dW2": 2 * tdf, "step/dW1": 2 * tdf}.get(stage)
 
 
-KERNEL_OF_STAGE = {"step/y1+sqrelu_vnm_compress": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dy2+dsqrelu_vnm": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
-                   "step/y1": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dy2": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
-                   "step/y3": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "step/dX": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
-                   "step/dW2": "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>", "step/dW1": "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>",
-                   "router/y1c+sqrelu+2:4": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "router/dy2c": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
-                   "router/y3": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>", "router/dX": "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>",
-                   "router/dW2.T": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>", "router/dW1": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>"}
+KERNEL_OF_STAGE = {"step/y1+sqrelu_vnm_compress": SPARSE_GEMM, "step/dy2+dsqrelu_vnm": SPARSE_GEMM, "step/y1": SPARSE_GEMM, "step/dy2": SPARSE_GEMM,
+                   "step/y3": SPARSE_GEMM, "step/dX": SPARSE_GEMM, "step/dW2": WGRAD, "step/dW1": WGRAD,
+                   "router/y1c+sqrelu+2:4": SPARSE_GEMM, "router/dy2c+dsqrelu": SPARSE_GEMM, "router/y3": SPARSE_GEMM, "router/dX": SPARSE_GEMM,
+                   "router/dW2.T": DENSE_GEMM, "router/dW1": DENSE_GEMM}
 
 
 def main():
@@ -52,14 +58,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="1b", help="tiny | 1b | 7b | 70b | moe_expert | moe (8 experts, 16384 tokens routed top-2, grouped launches)")
+    ap.add_argument("--workload", default="70b", help="headline workload: tiny | 1b | 7b | 70b | moe_expert | moe (8 experts, 16384 tokens routed top-2, grouped launches)")
     ap.add_argument("--zero-fraction", type=float, default=0.90)
     ap.add_argument("--mode", default="hard", choices=["hard", "soft"])
     ap.add_argument("--M", type=int, default=8, choices=[8, 16, 32, 64],
-                    help="V:2:M block width of the activation format (Table 5); 8 is the headline configuration, wider blocks run the unfused path")
+                    help="V:2:M block width of the activation format (Table 5); 8 is the headline configuration")
     ap.add_argument("--router", action="store_true",
                     help="time the neuron-level router's training step (Section 3.3: ffn_router_full_step = routing + grouped step, M / 4 experts) instead of the magnitude-based V:N:M step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true", help="skip the other configurations, the stand-alone kernels and the micro-benchmarks (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference kernel for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -69,88 +76,147 @@ def main():
     import numpy as np
     import torch
     import paper_2602_06183_amd as sffn
-    from workload import CONFIGS, make_ffn_inputs, make_moe_inputs
+    from workload import CONFIGS, make_ffn_inputs, make_moe_inputs, make_router_inputs
+    from workload.synth import neuron_std, bias_for_zero_fraction
 
     sffn.load()                     # fails loudly when the HIP library is missing
     mode = sffn.MODE_SOFT if args.mode == "soft" else sffn.MODE_HARD
-    moe = args.workload == "moe"
-    M = args.M
-    if moe and M != 8:
-        sys.exit("bench.py: the grouped step is built for M = 8 only")
-    if moe and args.router:
-        sys.exit("bench.py: --router runs on the single-FFN workloads")
-    if moe:
-        _, D, F = CONFIGS["moe_expert"]
-        inp = make_moe_inputs(16384, 8, 2, D, F, seed=0, zero_fraction=args.zero_fraction)
-        seg = [int(v) for v in inp["seg"]]
-        T = int(inp["counts"].sum())            # flop are counted on routed tokens, not on the 64-row padding
-    else:
-        T, D, F = CONFIGS[args.workload]
-        inp = make_ffn_inputs(T, D, F, seed=0, zero_fraction=args.zero_fraction)
-
-    def sffn_bits(t):            # device bf16 tensor -> numpy bit patterns (for the CPU oracle leg)
-        return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+    if args.workload == "moe" and (args.M != 8 or args.router):
+        sys.exit("bench.py: the grouped (moe) step runs the magnitude-based M = 8 format")
+    try:
+        torch.backends.cuda.preferred_blas_library("hipblaslt")
+    except Exception:
+        pass
 
     def dev(a):
         if a.dtype == np.uint16:
             return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
         return torch.from_numpy(a).cuda()
 
-    X, W1, W2, b1, dY = (dev(inp[k]) for k in ("X", "W1", "W2", "b1", "dY"))
-    if args.router:
-        from workload import make_router_inputs
-        means = dev(make_router_inputs(64, D, 4 * M, M, seed=0)["means"])
-        step = sffn.FfnRouterStep(T, D, F, M, mode)
-    else:
-        step = sffn.FfnStepGrouped(seg, D, F, mode) if moe else sffn.FfnStep(T, D, F, mode, M=M)
-    flops = 12.0 * T * D * F
+    def bits(t):            # device bf16 tensor -> numpy bit patterns (for the CPU oracle leg)
+        return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
 
-    # ---- dense bf16 FFN step on hipBLASLt (torch.matmul), same shapes, same process -------------
-    try:
-        torch.backends.cuda.preferred_blas_library("hipblaslt")
-    except Exception:
-        pass
-    b1h = b1.to(torch.bfloat16)
-    Tp = X.shape[0]                                       # rows including padding
-    y1 = torch.empty((Tp, F), dtype=torch.bfloat16, device="cuda")
-    y2, dy2, dy1 = torch.empty_like(y1), torch.empty_like(y1), torch.empty_like(y1)
-    y3, dXd = torch.empty((Tp, D), dtype=torch.bfloat16, device="cuda"), torch.empty((Tp, D), dtype=torch.bfloat16, device="cuda")
-    dW1d, dW2d = torch.empty_like(W1), torch.empty_like(W2)
-
-    def dense_ffn(X, W1, W2, b1h, dY, y1, y2, y3, dy2, dy1, dXd, dW1d, dW2d):
-        torch.addmm(b1h, X, W1.t(), out=y1)              # eq. (1)
-        torch.clamp_min(y1, 0.0, out=y2); y2.mul_(y2)             # eq. (2)
-        torch.mm(y2, W2.t(), out=y3)                     # eq. (3)
-        torch.mm(dY, W2, out=dy2)                        # eq. (4)
-        torch.mm(dY.t(), y2, out=dW2d)                   # eq. (5)
-        torch.clamp_min(y1, 0.0, out=dy1); dy1.mul_(dy2).mul_(2.0) # eq. (6)
-        torch.mm(dy1, W1, out=dXd)                       # eq. (7)
-        torch.mm(dy1.t(), X, out=dW1d)                   # eq. (8)
-
-    if moe:     # the dense MoE layer: the same eight calls per expert on its segment
-        parts = [tuple(t[seg[e]:seg[e + 1]] for t in (X, dY, y1, y2, y3, dy2, dy1, dXd)) for e in range(len(seg) - 1)]
-
-        def dense_step():
-            for e, (Xe, dYe, y1e, y2e, y3e, dy2e, dy1e, dXe) in enumerate(parts):
-                dense_ffn(Xe, W1[e], W2[e], b1h[e], dYe, y1e, y2e, y3e, dy2e, dy1e, dXe, dW1d[e], dW2d[e])
-    else:
-        def dense_step():
-            dense_ffn(X, W1, W2, b1h, dY, y1, y2, y3, dy2, dy1, dXd, dW1d, dW2d)
-
-    if args.router:
-        def sparse_step():          # Alg. 3 steps 1-2 and the grouped step in one call; the run offsets stay on the device
-            step.full(means, X, W1, W2, b1, dY)
-    else:
-        def sparse_step():
-            step(X, W1, W2, b1, dY)
-
-    def timed(fn, n):
+    def timed(fn, n):       # wall clock around n calls, synchronised on both sides
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(n):
             fn()
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / n
+
+    def ms_of(fn, n=10):    # events on torch's current stream, which is the stream the binding launches on
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    def free():
+        gc.collect()
+        torch.cuda.empty_cache()
+
+    class Workload:
+        """Device tensors of one configuration, the sparse step and the dense baseline step on them."""
+
+        def __init__(self, name, zero_fraction, M=8, router=False, host=None):
+            self.name, self.zf, self.M, self.router, self.moe = name, zero_fraction, M, router, name == "moe"
+            if self.moe:
+                _, self.D, self.F = CONFIGS["moe_expert"]
+                inp = host or make_moe_inputs(16384, 8, 2, self.D, self.F, seed=0, zero_fraction=zero_fraction)
+                self.seg = [int(v) for v in inp["seg"]]
+                self.T = int(inp["counts"].sum())           # flop are counted on routed tokens, not on the 64-row padding
+            else:
+                self.T, self.D, self.F = CONFIGS[name]
+                inp = host or make_ffn_inputs(self.T, self.D, self.F, seed=0, zero_fraction=zero_fraction)
+            self.host = inp
+            self.X, self.W1, self.W2, self.b1, self.dY = (dev(inp[k]) for k in ("X", "W1", "W2", "b1", "dY"))
+            T, D, F = self.T, self.D, self.F
+            if router:
+                self.means = dev(make_router_inputs(64, D, 4 * M, M, seed=0)["means"])
+                self.step = sffn.FfnRouterStep(T, D, F, M, mode)
+            else:
+                self.step = sffn.FfnStepGrouped(self.seg, D, F, mode) if self.moe else sffn.FfnStep(T, D, F, mode, M=M)
+            self.flops = 12.0 * T * D * F
+            # dense bf16 FFN step: six hipBLASLt GEMMs (torch.matmul) and the two element-wise equations, one pass each
+            self.b1h = self.b1.to(torch.bfloat16)
+            Tp = self.X.shape[0]                             # rows including padding
+            bf = lambda *shape: torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+            self.y1, self.y2, self.dy2, self.dy1 = bf(Tp, F), bf(Tp, F), bf(Tp, F), bf(Tp, F)
+            self.y3, self.dXd = bf(Tp, D), bf(Tp, D)
+            self.dW1d, self.dW2d = torch.empty_like(self.W1), torch.empty_like(self.W2)
+            if self.moe:
+                self.parts = [tuple(t[self.seg[e]:self.seg[e + 1]] for t in (self.X, self.dY, self.y1, self.y2, self.y3, self.dy2, self.dy1, self.dXd))
+                              for e in range(len(self.seg) - 1)]
+
+        @staticmethod
+        def _dense_ffn(X, W1, W2, b1h, dY, y1, y2, y3, dy2, dy1, dXd, dW1d, dW2d, elementwise=True):
+            torch.addmm(b1h, X, W1.t(), out=y1)              # eq. (1)
+            if elementwise:
+                sffn.dense_sqrelu(y1, y2)                    # eq. (2), one pass
+            torch.mm(y2, W2.t(), out=y3)                     # eq. (3)
+            torch.mm(dY, W2, out=dy2)                        # eq. (4)
+            torch.mm(dY.t(), y2, out=dW2d)                   # eq. (5)
+            if elementwise:
+                sffn.dense_dsqrelu(dy2, y1, dy1)             # eq. (6), one pass
+            torch.mm(dy1, W1, out=dXd)                       # eq. (7)
+            torch.mm(dy1.t(), X, out=dW1d)                   # eq. (8)
+
+        def dense_step(self, elementwise=True):
+            if self.moe:     # the dense MoE layer: the same eight calls per expert on its segment
+                for e, (Xe, dYe, y1e, y2e, y3e, dy2e, dy1e, dXe) in enumerate(self.parts):
+                    self._dense_ffn(Xe, self.W1[e], self.W2[e], self.b1h[e], dYe, y1e, y2e, y3e, dy2e, dy1e, dXe, self.dW1d[e], self.dW2d[e], elementwise)
+            else:
+                self._dense_ffn(self.X, self.W1, self.W2, self.b1h, self.dY, self.y1, self.y2, self.y3, self.dy2, self.dy1, self.dXd,
+                                self.dW1d, self.dW2d, elementwise)
+
+        def sparse_step(self):
+            if self.router:      # Alg. 3 steps 1-2 and the grouped step in one call; the run offsets stay on the device
+                self.step.full(self.means, self.X, self.W1, self.W2, self.b1, self.dY)
+            else:
+                self.step(self.X, self.W1, self.W2, self.b1, self.dY)
+
+        def measure(self, steps, warmup):
+            for _ in range(warmup):
+                self.sparse_step()
+                self.dense_step()
+            r = {"ms_sparse": timed(self.sparse_step, steps), "ms_dense": timed(self.dense_step, steps)}      # the timed region: exactly `steps` steps
+            r["ms_dense_gemms"] = timed(lambda: self.dense_step(False), steps)
+            r["ms_sparse2"], r["ms_dense2"] = timed(self.sparse_step, steps), timed(self.dense_step, steps)  # second, interleaved pass: clock drift check
+            return r
+
+        def retained_l1(self):
+            """How much of the activation's L1 mass the V:N:M format keeps (sum of kept y2 / sum of all y2) and the ReLU zero
+            fraction: one extra, untimed step that also stores the dense y1; plain torch reductions, measurement only."""
+            if self.router or self.moe:
+                return None, None
+            self.y2 = self.dy2 = self.dy1 = None             # the dense baseline's buffers are no longer needed
+            free()
+            chk = sffn.FfnStep(self.T, self.D, self.F, mode, keep_dense=True, M=self.M)
+            chk(self.X, self.W1, self.W2, self.b1, self.dY)
+            sv = chk.saved()
+            y2_all = torch.clamp_min(sv["y1"].float(), 0.0).square_().to(torch.bfloat16)        # eq. (2), rounded as the kernel does
+            retained = round(float(sv["y2_vals"].float().sum() / y2_all.float().sum()), 4)
+            zero_frac = round(float((y2_all == 0).float().mean()), 4)
+            return retained, zero_frac
+
+        def summary(self, r, with_l1=True):
+            T, D, F = self.T, self.D, self.F
+            tf = self.flops / (r["ms_sparse"] * 1e-3) / 1e12
+            out = {"T": T, "d_model": D, "d_ff": F, "zero_fraction": self.zf, "ms_per_step": round(r["ms_sparse"], 4),
+                   "dense_ms_per_step": round(r["ms_dense"], 4), "dense_gemms_only_ms": round(r["ms_dense_gemms"], 4),
+                   "speedup_vs_dense": round(r["ms_dense"] / r["ms_sparse"], 4),
+                   "speedup_vs_dense_gemms_only": round(r["ms_dense_gemms"] / r["ms_sparse"], 4),
+                   "tflops_dense_equiv": round(tf, 2), "frac_of_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                   # the method's own non-zero multiply-adds: 4 T D F flop per step (eqs. (1), (4): T D F each; the four others T D F / 2)
+                   # (V:2:M activations: eqs. (3), (5), (7), (8) shrink to 4 T D F / M flop each)
+                   "algorithmic_frac_of_mfma_peak": round(tf * (2.0 + 16.0 / self.M) / 12.0 / MFMA_BF16_PEAK_TFLOPS, 4) if not self.router else None}
+            if with_l1:
+                out["retained_l1_fraction"], out["relu_zero_fraction"] = self.retained_l1()
+            return out
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
@@ -160,133 +226,47 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        sparse_step()
-        dense_step()
-    ms_sparse = timed(sparse_step, args.steps)          # the timed region: exactly --steps steps
-    ms_dense = timed(dense_step, args.steps)
-    ms_sparse2 = timed(sparse_step, args.steps)         # second, interleaved pass: clock drift check
-    ms_dense2 = timed(dense_step, args.steps)
+    # ================= headline workload ===========================================================================
+    M = args.M
+    hw = Workload(args.workload, args.zero_fraction, M, args.router)
+    T, D, F = hw.T, hw.D, hw.F
+    res = hw.measure(args.steps, args.warmup)
 
     # ---- per-launch durations from HIP events on the stream the kernels run on --------------------
     sffn.profile_enable(True)
     acc = {}
     nprof = max(3, min(10, args.steps))
     for _ in range(nprof):
-        sparse_step()
+        hw.sparse_step()
         for name, ms in sffn.profile_read():
             acc[name] = acc.get(name, 0.0) + ms / nprof
     sffn.profile_enable(False)
     by_kernel = {}
+    kos = dict(KERNEL_OF_STAGE)
     if "step/dX" in acc and "step/W1.T" not in acc and M == 8:      # eq. (7) ran on the gathered-row kernel (no transpose of W1 in the step)
-        KERNEL_OF_STAGE["step/dX"] = "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>"
-    if M != 8:      # the wide-block path contracts the expanded activation with the dense-operand variant of the tile kernel
-        KERNEL_OF_STAGE.update({"step/dW2": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>", "step/dW1": "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>"})
+        kos["step/dX"] = "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>"
     for name, ms in acc.items():
-        k = KERNEL_OF_STAGE.get(name, name)
-        by_kernel.setdefault(k, []).append((name, ms))
+        by_kernel.setdefault(kos.get(name, name), []).append((name, ms))
     dom_kernel = max(by_kernel, key=lambda k: sum(ms for _, ms in by_kernel[k]))
     launches = by_kernel[dom_kernel]
     avg_ms = sum(ms for _, ms in launches) / len(launches)
     alg = sum(algorithmic_flops(n, T, D, F, M) or 0.0 for n, _ in launches) / len(launches)
     exe = sum(executed_flops(n, T, D, F, M) or 0.0 for n, _ in launches) / len(launches)
     achieved = alg / (avg_ms * 1e-3) / 1e12
+    # HBM bytes per launch of that kernel: from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes of this same command, scaled by a
+    # plain copy (the summaries and the scale factors are in profiles/; counters cannot be read from inside the timed process)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
-    if os.path.exists(tpath) and M == 8:
+    if os.path.exists(tpath) and M == 8 and not args.router:
         traffic = json.load(open(tpath)).get(dom_kernel)
-    roofline = {"bound": "mfma", "kernel": dom_kernel, "launches_per_step": len(launches), "avg_launch_ms": round(avg_ms, 4),
+    roofline = {"bound": "mfma", "kernel": dom_kernel, "launches_per_step": len(launches), "launches": [n for n, _ in launches],
+                "avg_launch_ms": round(avg_ms, 4), "algorithmic_flop_per_launch": alg,
                 "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
                 "issued": round(exe / (avg_ms * 1e-3) / 1e12, 2), "issued_frac": round(exe / (avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    head = hw.summary(res)
 
-    # ---- the two compressors alone (HBM-bound; algorithmic bytes = input read once + packed outputs) -----------
-    def ms_of(fn, n=10):
-        fn()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)   # the binding launches on torch's current stream
-        e0.record()
-        for _ in range(n):
-            fn()
-        e1.record()
-        e1.synchronize()
-        return e0.elapsed_time(e1) / n
-
-    def gbs(fn, nbytes, n=10):
-        return round(nbytes / (ms_of(fn, n) * 1e-3) / 1e9, 1)
-
-    w1_one, w2_one = (W1[0], W2[0]) if moe else (W1, W2)
-    y1_one = y1[:min(Tp, 16384)]
-    kernels = {
-        "prune24_compress(W1) GB/s": gbs(lambda: sffn.prune24_compress(w1_one, False, mode), 3.125 * F * D),
-        "prune24_compress(W2, trans) GB/s": gbs(lambda: sffn.prune24_compress(w2_one, True, mode), 3.125 * F * D),
-        "sqrelu_vnm_compress GB/s": gbs(lambda: sffn.sqrelu_vnm_compress(y1_one), (2 + 0.5 + 0.0625 + 1.0 / 128) * y1_one.shape[0] * F),
-        "hbm_peak GB/s": HBM_PEAK_GBS,
-    }
-    for m in (16, 32, 64):       # Table 5's block widths: bytes = input + packed values (2 of m) + metadata + column offsets
-        kernels["sqrelu_vnm_compress 64:2:%d GB/s" % m] = gbs(lambda: sffn.sqrelu_vnm_compress(y1_one, 64, m),
-                                                              (2 + 4.0 / m + 0.5 / m + 4.0 / (64 * m)) * y1_one.shape[0] * F)
-    # the paper's 2:4 micro-benchmark shape (Section 5.2.3): (m, n, k) = (4096, 16384, 4096), pruning included and excluded
-    gx = torch.randn((4096, 4096), device="cuda").to(torch.bfloat16)
-    gw = (torch.randn((16384, 4096), device="cuda") * 0.02).to(torch.bfloat16)
-    gout = torch.empty((4096, 16384), dtype=torch.bfloat16, device="cuda")
-    t_d = ms_of(lambda: torch.mm(gx, gw.t(), out=gout))
-    gv, gm = sffn.prune24_compress(gw, False, mode)
-    t_s = ms_of(lambda: sffn.spmm24_fwd(gx, gv, gm))
-    t_p = ms_of(lambda: sffn.prune24_compress(gw, False, mode))
-    gemm24 = {"shape_mnk": [4096, 16384, 4096], "dense_ms": round(t_d, 4), "spmm24_ms": round(t_s, 4), "prune24_ms": round(t_p, 4),
-              "speedup_vs_dense": round(t_d / t_s, 3), "speedup_with_pruning": round(t_d / (t_s + t_p), 3)}
-    del gx, gw, gout, gv, gm
-
-    # ---- the activation GEMM alone for every block width of Table 5, against the dense GEMM of the same shape
-    #      (Section 5.2.3's micro-benchmark): out[T, D] = y2v[T, F] @ W1[F, D], eq. (7)'s orientation ------------------
-    venom = None
-    if not moe:
-        dense_out = torch.empty((y1_one.shape[0], D), dtype=torch.bfloat16, device="cuda")
-        t_dense = ms_of(lambda: torch.mm(y1_one, w1_one, out=dense_out))
-        venom = {"shape": "[%d, %d] x [%d, %d]" % (y1_one.shape[0], F, F, D), "dense_ms": round(t_dense, 4)}
-        for m in (8, 16, 32, 64):
-            pack = sffn.sqrelu_vnm_compress(y1_one, 64, m)
-            t = ms_of(lambda: sffn.vnm_spmm(pack[0], pack[1], pack[2], w1_one, 1, 64, m))
-            venom["64:2:%d" % m] = {"ms": round(t, 4), "speedup_vs_dense": round(t_dense / t, 3)}
-        del dense_out
-
-    # ---- conversion to V:N:M by the neuron-level router (Section 3.3; the three steps whose cost Section 3.4 discusses):
-    #      routing (reads X once), stable grouping + gather of X, grouped matmul that emits V:N:M; E = M / 4 experts ----
-    router = None
-    if not moe:
-        from workload import make_router_inputs   # only the expert means are new; X, W1, b1 are the step's
-        router = {"dense_y1_ms": round(ms_of(lambda: torch.addmm(b1h, X, W1.t(), out=y1)), 4)}
-        for m in (8, 16, 32, 64):
-            means_m = dev(make_router_inputs(64, D, 4 * m, m, seed=0)["means"])
-            t_route = ms_of(lambda: sffn.venom_route_launch(X, means_m, m))
-            rr = sffn.venom_route(X, means_m, m)
-            ws_r = torch.empty((sffn.load().sffn_venom_matmul_workspace_bytes(T, D, F, m),), dtype=torch.uint8, device="cuda")
-            t_mm = ms_of(lambda: sffn.venom_expert_matmul(X, rr["perm"], rr["seg"], W1, b1, m, mode, keep_y1c=False, workspace=ws_r))
-            router["64:2:%d" % m] = {"experts": m // 4, "rows": int(rr["perm"].shape[0]), "route_and_group_ms": round(t_route, 4),
-                                     "route_and_group_GBs_of_X": round(T * D * 2 / (t_route * 1e-3) / 1e9, 1),
-                                     "gather_prune_matmul_ms": round(t_mm, 4),
-                                     "conversion_vs_dense_y1": round(router["dense_y1_ms"] / (t_route + t_mm), 3)}
-            del ws_r, rr, means_m
-
-    # ---- how much of the activation's L1 mass the V:N:M format keeps (sum of kept y2 / sum of all y2): one extra,
-    #      untimed step that also stores the dense y1; plain torch reductions, measurement only ------------------
-    retained = None
-    if args.router:
-        zero_frac = None
-    elif not moe:
-        del y2, dy2, dy1                                   # the dense baseline's buffers are no longer needed
-        chk = sffn.FfnStep(T, D, F, mode, keep_dense=True, M=M)
-        chk(X, W1, W2, b1, dY)
-        sv = chk.saved()
-        y2_all = torch.clamp_min(sv["y1"].float(), 0.0).square_().to(torch.bfloat16)        # eq. (2), rounded as the kernel does
-        retained = round(float(sv["y2_vals"].float().sum() / y2_all.float().sum()), 4)
-        zero_frac = round(float((y2_all == 0).float().mean()), 4)
-        del chk, sv, y2_all
-    else:
-        zero_frac = None
-
-    # ---- CPU oracle on the host cores: a bounded token sample of the same workload ---------------
+    # ---- CPU oracle on the host cores: a bounded sample of the same workload -------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -295,42 +275,151 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             cores = os.cpu_count()
-        Ts = min(T, max(64, (int(3.0e11 / (12.0 * D * F)) // 64) * 64))      # about 0.3 TFLOP of fp64 matmul
-        w1o, w2o, b1o = (inp[k][0] if moe else inp[k] for k in ("W1", "W2", "b1"))    # moe: expert 0 on its first tokens
+        # a narrower layer of the same d_model: the first Fs hidden units (whole V:N:M column blocks; hidden units only meet in
+        # the sums of Y3 and dX) on the first Ts tokens, sized for roughly 10-30 s of numpy work
+        Fs = F if F * D <= (1 << 25) else max(512, ((1 << 25) // D) // 64 * 64)
+        Ts = min(T, max(64, (int(2.0e11 / (12.0 * D * Fs)) // 64) * 64))
+        inp = hw.host
+        w1o, w2o, b1o = (inp[k][0] if hw.moe else inp[k] for k in ("W1", "W2", "b1"))    # moe: expert 0 on its first tokens
+        w1o, w2o, b1o = w1o[:Fs], np.ascontiguousarray(w2o[:, :Fs]), b1o[:Fs]
         t0 = time.perf_counter()
         if args.router:
-            oracle.ffn_router_step_ref(inp["X"][:Ts], w1o, w2o, b1o, inp["dY"][:Ts], sffn_bits(means), M, mode)
+            oracle.ffn_router_step_ref(inp["X"][:Ts], w1o, w2o, b1o, inp["dY"][:Ts], bits(hw.means), M, mode)
         else:
             oracle.ffn_sparse_step_ref(inp["X"][:Ts], w1o, w2o, b1o, inp["dY"][:Ts], mode, 64, M)
         dt = time.perf_counter() - t0
-        cpu = {"value": round(12.0 * Ts * D * F / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-               "sample": "oracle.%s on the first %d of %d tokens (same D, F, weights%s), %.1f s"
-                         % ("ffn_router_step_ref" if args.router else "ffn_sparse_step_ref", Ts, T, " of expert 0" if moe else "", dt)}
+        cpu = {"value": round(12.0 * Ts * D * Fs / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+               "sample": "oracle.%s on the first %d of %d tokens and the first %d of %d hidden units (same d_model, weights%s, bias), %.1f s"
+                         % ("ffn_router_step_ref" if args.router else "ffn_sparse_step_ref", Ts, T, Fs, F, " of expert 0" if hw.moe else "", dt)}
 
-    value = flops / (ms_sparse * 1e-3) / 1e12
+    # ================= the other configurations, stand-alone kernels, micro-benchmarks =============================
+    configs, kernels, gemm24, venom, router = None, None, None, None, None
+    if not args.headline_only and not args.router and M == 8:
+        esteps, ewarm = max(3, min(args.steps, 10)), max(1, min(args.warmup, 2))
+        configs = {}
+        key = lambda name, zf: "%s@%.2f" % (name, zf)
+        configs[key(hw.name, hw.zf)] = dict(head, headline=True)
+        # configs[3]'s sweep of the ReLU zero fraction: same tensors, only the bias shifts
+        if hw.name == "70b":
+            std = neuron_std(hw.host["W1"])
+            for zf in (0.50, 0.75, 0.90, 0.95):
+                if abs(zf - hw.zf) < 1e-9:
+                    continue
+                hw.b1 = dev(bias_for_zero_fraction(std, zf))
+                hw.b1h, hw.zf = hw.b1.to(torch.bfloat16), zf
+                bf = lambda *shape: torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+                hw.y2, hw.dy2, hw.dy1 = bf(T, F), bf(T, F), bf(T, F)
+                configs[key("70b", zf)] = hw.summary(hw.measure(esteps, ewarm))
+        host_1b = None
+        del hw
+        free()
+        for name in ("tiny", "1b", "7b", "moe"):
+            if key(name, 0.90) in configs:
+                continue
+            w = Workload(name, 0.90)
+            configs[key(name, 0.90)] = w.summary(w.measure(esteps if name != "tiny" else 50, ewarm))
+            if name == "1b":
+                host_1b = w.host
+            del w
+            free()
+
+        def gbs(fn, nbytes, n=12):
+            return round(nbytes / (ms_of(fn, n) * 1e-3) / 1e9, 1)
+
+        # ---- the two compressors alone at the 7B shape (HBM-bound; algorithmic bytes = input read once + packed outputs).
+        #      Every launch reads a different copy of its input (4 weight copies = 512 MiB, 2 activation copies = 1 GiB, more
+        #      than the 256 MB last-level cache), so the rate is an HBM rate and not a cache-resident one. --------------
+        T7, D7, F7 = CONFIGS["7b"]
+        wsrc = [(torch.randn((F7, D7), device="cuda") * 0.02).to(torch.bfloat16) for _ in range(4)]
+        ysrc = [(torch.randn((T7, F7), device="cuda") - 1.2816).to(torch.bfloat16) for _ in range(2)]
+        turn = [0]
+
+        def rot(pool):
+            turn[0] += 1
+            return pool[turn[0] % len(pool)]
+        kernels = {
+            "shape": "7b: W [%d, %d], y1 [%d, %d]; inputs rotated through %d / %d copies" % (F7, D7, T7, F7, len(wsrc), len(ysrc)),
+            "prune24_compress(W1) GB/s": gbs(lambda: sffn.prune24_compress(rot(wsrc), False, mode), 3.125 * F7 * D7),
+            "prune24_compress(W2, trans) GB/s": gbs(lambda: sffn.prune24_compress(rot(wsrc), True, mode), 3.125 * F7 * D7),
+            "sqrelu_vnm_compress GB/s": gbs(lambda: sffn.sqrelu_vnm_compress(rot(ysrc)), (2 + 0.5 + 0.0625 + 1.0 / 128) * T7 * F7),
+            "hbm_peak GB/s": HBM_PEAK_GBS,
+        }
+        for m in (16, 32, 64):       # Table 5's block widths: bytes = input + packed values (2 of m) + metadata + column offsets
+            kernels["sqrelu_vnm_compress 64:2:%d GB/s" % m] = gbs(lambda: sffn.sqrelu_vnm_compress(rot(ysrc), 64, m),
+                                                                  (2 + 4.0 / m + 0.5 / m + 4.0 / (64 * m)) * T7 * F7)
+        del wsrc, ysrc
+        free()
+
+        # ---- the paper's 2:4 micro-benchmark shape (Section 5.2.3): (m, n, k) = (4096, 16384, 4096), pruning included and excluded
+        gx = torch.randn((4096, 4096), device="cuda").to(torch.bfloat16)
+        gw = (torch.randn((16384, 4096), device="cuda") * 0.02).to(torch.bfloat16)
+        gout = torch.empty((4096, 16384), dtype=torch.bfloat16, device="cuda")
+        t_d = ms_of(lambda: torch.mm(gx, gw.t(), out=gout))
+        gv, gm = sffn.prune24_compress(gw, False, mode)
+        t_s = ms_of(lambda: sffn.spmm24_fwd(gx, gv, gm))
+        t_p = ms_of(lambda: sffn.prune24_compress(gw, False, mode))
+        gemm24 = {"shape_mnk": [4096, 16384, 4096], "dense_ms": round(t_d, 4), "spmm24_ms": round(t_s, 4), "prune24_ms": round(t_p, 4),
+                  "speedup_vs_dense": round(t_d / t_s, 3), "speedup_with_pruning": round(t_d / (t_s + t_p), 3)}
+        del gx, gw, gout, gv, gm
+
+        # ---- at the 1B shape: the activation GEMM alone for every block width of Table 5 against the dense GEMM of the same
+        #      shape (Section 5.2.3's Venom micro-benchmark; out[T, D] = y2v[T, F] @ W1[F, D], eq. (7)'s orientation), and the
+        #      conversion to V:N:M by the neuron-level router (Section 3.3; the three steps whose cost Section 3.4 discusses):
+        #      routing (reads X once), stable grouping + gather of X, grouped matmul that emits V:N:M; E = M / 4 experts ----
+        T1, D1, F1 = CONFIGS["1b"]
+        h1 = host_1b or make_ffn_inputs(T1, D1, F1, seed=0)
+        X1, W11, b11 = dev(h1["X"]), dev(h1["W1"]), dev(h1["b1"])
+        y1_1 = torch.addmm(b11.to(torch.bfloat16), X1, W11.t())
+        dense_out = torch.empty((T1, D1), dtype=torch.bfloat16, device="cuda")
+        t_dense = ms_of(lambda: torch.mm(y1_1, W11, out=dense_out))
+        venom = {"shape": "[%d, %d] x [%d, %d]" % (T1, F1, F1, D1), "dense_ms": round(t_dense, 4)}
+        for m in (8, 16, 32, 64):
+            pack = sffn.sqrelu_vnm_compress(y1_1, 64, m)
+            t = ms_of(lambda: sffn.vnm_spmm(pack[0], pack[1], pack[2], W11, 1, 64, m))
+            venom["64:2:%d" % m] = {"ms": round(t, 4), "speedup_vs_dense": round(t_dense / t, 3)}
+        del dense_out
+        b1h1 = b11.to(torch.bfloat16)
+        router = {"shape": "1b", "dense_y1_ms": round(ms_of(lambda: torch.addmm(b1h1, X1, W11.t(), out=y1_1)), 4)}
+        for m in (8, 16, 32, 64):
+            means_m = dev(make_router_inputs(64, D1, 4 * m, m, seed=0)["means"])
+            t_route = ms_of(lambda: sffn.venom_route_launch(X1, means_m, m))
+            rr = sffn.venom_route(X1, means_m, m)
+            ws_r = torch.empty((sffn.load().sffn_venom_matmul_workspace_bytes(T1, D1, F1, m),), dtype=torch.uint8, device="cuda")
+            t_mm = ms_of(lambda: sffn.venom_expert_matmul(X1, rr["perm"], rr["seg"], W11, b11, m, mode, keep_y1c=False, workspace=ws_r))
+            router["64:2:%d" % m] = {"experts": m // 4, "rows": int(rr["perm"].shape[0]), "route_and_group_ms": round(t_route, 4),
+                                     "route_and_group_GBs_of_X": round(T1 * D1 * 2 / (t_route * 1e-3) / 1e9, 1),
+                                     "gather_prune_matmul_ms": round(t_mm, 4),
+                                     "conversion_vs_dense_y1": round(router["dense_y1_ms"] / (t_route + t_mm), 3)}
+            del ws_r, rr, means_m
+
+    if args.workload == "moe":
+        wl = ("moe: 8 experts, 16384 tokens routed top-2 = %d token slots in 64-row aligned segments, d_model=%d, d_ff=%d per expert, 2:4 weights (%s), "
+              "V:N:M 64:2:8 SquaredReLU, zero fraction %.2f, seed 0; one grouped launch per stage" % (T, D, F, args.mode, args.zero_fraction))
+    else:
+        wl = ("%s: one FFN layer, T=%d tokens, d_model=%d, d_ff=%d, 2:4 weights (%s), V:N:M 64:2:%d SquaredReLU%s, zero fraction %.2f, seed 0"
+              % (args.workload, T, D, F, args.mode, M,
+                 " produced by the neuron-level router (%d experts, routing + grouping inside the timed step)" % (M // 4) if args.router else "",
+                 args.zero_fraction))
     out = {
         "metric": "sparse FFN fwd+bwd TFLOP/s (dense-equiv) & speedup vs dense bf16, 1 MI355X",
-        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_sparse, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": head["tflops_dense_equiv"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": ("moe: 8 experts, 16384 tokens routed top-2 = %d token slots in segments %s (64-row aligned), d_model=%d, d_ff=%d per expert, "
-                                "2:4 weights (%s), V:N:M 64:2:8 SquaredReLU, zero fraction %.2f, seed 0; one grouped launch per stage"
-                                % (T, seg, D, F, args.mode, args.zero_fraction)) if moe else
-                               "%s: one FFN layer, T=%d tokens, d_model=%d, d_ff=%d, 2:4 weights (%s), V:N:M 64:2:%d SquaredReLU%s, zero fraction %.2f, seed 0"
-                               % (args.workload, T, D, F, args.mode, M,
-                                  " produced by the neuron-level router (%d experts, routing + grouping inside the timed step)" % (M // 4) if args.router else "",
-                                  args.zero_fraction)},
-        "frac_of_mfma_peak": round(value / MFMA_BF16_PEAK_TFLOPS, 4),
-        "dense_ms_per_step": round(ms_dense, 4), "dense_tflops": round(flops / (ms_dense * 1e-3) / 1e12, 2),
-        "dense_frac_of_mfma_peak": round(flops / (ms_dense * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-        "speedup_vs_dense": round(ms_dense / ms_sparse, 4),
-        "second_pass": {"ms_per_step": round(ms_sparse2, 4), "dense_ms_per_step": round(ms_dense2, 4)},
+        "config": {"workload": wl},
+        "frac_of_mfma_peak": head["frac_of_mfma_peak"], "algorithmic_frac_of_mfma_peak": head["algorithmic_frac_of_mfma_peak"],
+        "dense_ms_per_step": head["dense_ms_per_step"], "dense_gemms_only_ms": head["dense_gemms_only_ms"],
+        "dense_baseline": "6 hipBLASLt bf16 GEMMs (torch.mm / addmm) + eq. (2) and eq. (6) as one-pass element-wise kernels; dense_gemms_only_ms leaves the two element-wise kernels out",
+        "dense_tflops": round(12.0 * T * D * F / (head["dense_ms_per_step"] * 1e-3) / 1e12, 2),
+        "dense_frac_of_mfma_peak": round(12.0 * T * D * F / (head["dense_ms_per_step"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "speedup_vs_dense": head["speedup_vs_dense"], "speedup_vs_dense_gemms_only": head["speedup_vs_dense_gemms_only"],
+        "second_pass": {"ms_per_step": round(res["ms_sparse2"], 4), "dense_ms_per_step": round(res["ms_dense2"], 4)},
         "stage_ms": {k: round(v, 4) for k, v in acc.items()},
+        "retained_l1_fraction": head.get("retained_l1_fraction"), "relu_zero_fraction": head.get("relu_zero_fraction"),
+        "configs": configs,
         "standalone_kernels": kernels,
         "venom_gemm_microbench": venom,
         "gemm24_microbench": gemm24,
         "router_conversion": router,
-        "retained_l1_fraction": retained, "relu_zero_fraction": zero_frac,
         "roofline": roofline, "cpu_baseline": cpu,
         "paper_context": "paper reports 1.4-1.5x for 2:4 GEMMs and 1.4-1.7x end-to-end on NVIDIA sparse tensor cores (Sections 1, 5.2.3); context, not a target",
     }

@@ -43,7 +43,7 @@ extern "C" {
 
 #define SFFN_OK            0
 #define SFFN_EINVAL       (-1)  /* null pointer, bad shape or alignment */
-#define SFFN_EUNSUPPORTED (-2)  /* valid request outside what is built (V != 64, M != 8, ...) */
+#define SFFN_EUNSUPPORTED (-2)  /* valid request outside what is built (V != 64, M not in {8, 16, 32, 64}, a dimension too large) */
 #define SFFN_EWORKSPACE   (-3)  /* workspace pointer null or too small */
 #define SFFN_EHIP         (-4)  /* a HIP launch failed; see sffn_last_error() */
 
@@ -71,9 +71,10 @@ typedef struct sffn_cfg {
 typedef struct sffn_ws_layout {
     size_t w1_vals, w1_meta;        /* sparsify24(W1):   [F, D/2] bf16, [F, D/8] u8 */
     size_t w2t_vals, w2t_meta;      /* sparsify24(W2.T): [F, D/2] bf16, [F, D/8] u8 */
-    size_t y1;                      /* [T, F] bf16, eq. (1) plus bias (filled only with SFFN_FLAG_KEEP_DENSE) */
+    size_t y1;                      /* [T, F] bf16, eq. (1) plus bias.  Present with SFFN_FLAG_KEEP_DENSE or M > 8; otherwise the
+                                     * region is empty (0 bytes) and the workspace is smaller by 2 * 2 T F bytes (y1 and dy2) */
     size_t y2_vals, y2_meta, colidx;/* V:N:M y2: [T, F/4] bf16, [T, F/16] u8, [T/64, F/8, 4] u8 */
-    size_t dy2;                     /* [T, F] bf16, eq. (4) (filled only with SFFN_FLAG_KEEP_DENSE) */
+    size_t dy2;                     /* [T, F] bf16, eq. (4); present under the same condition as y1 */
     size_t dy1_vals;                /* [T, F/4] bf16, eq. (6) in y2's slots */
     size_t y1_kept;                 /* T*F/4 bf16, y1 at y2's kept slots (what Alg. 2 line 1 needs of y1), stored as
                                      * [T/64][F/64][64 tokens][8 column blocks][2] */
@@ -83,7 +84,8 @@ typedef struct sffn_ws_layout {
 int         sffn_version(void);
 const char* sffn_last_error(void);
 
-/* Workspace sizes in bytes (0 on invalid arguments). */
+/* Workspace sizes in bytes (0 on invalid arguments: a dimension that is not a positive multiple of 64, V != 64, M outside
+ * {8, 16, 32, 64}, F not a multiple of 2 M).  The size depends on cfg->flags: see sffn_ws_layout.y1. */
 size_t sffn_workspace_bytes(const sffn_cfg* cfg);                       /* ffn_sparse_step */
 int    sffn_workspace_layout(const sffn_cfg* cfg, sffn_ws_layout* out); /* its layout */
 size_t sffn_vnm_spmm_workspace_bytes(int64_t T, int64_t N, int64_t Kfull, int w_kmajor);
@@ -119,7 +121,8 @@ int spmm24_dgrad(const uint16_t* dY, const uint16_t* wt_vals, const uint8_t* wt_
  * copy of Wd).  Route: when 4*Kfull/M is a multiple of 64 and at most 7168 (and M >= 16, or M = 8
  * with w_kmajor=1) only the kept rows of the contraction-major W take part (gathered per 64-token
  * block); otherwise the activation is contracted as a plain 2:4 matrix over all Kfull columns.
- * Both routes compute the same sums (fp32 accumulation order differs). */
+ * Both routes compute the same sums (fp32 accumulation order differs).  T is below 2^22 on the gathered route and
+ * below 65536 on the plain-2:4 route (SFFN_EUNSUPPORTED beyond, nothing enqueued). */
 int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_colidx,
              const uint16_t* Wd, int64_t ldw, int w_kmajor, int64_t T, int64_t N, int64_t Kfull,
              int V, int M, uint16_t* out, void* workspace, size_t ws_bytes, void* stream);
@@ -224,6 +227,13 @@ int ffn_sparse_step_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* s
  * names[i] (static strings naming the stage).  Not thread-safe; enable/disable create/destroy events. */
 int sffn_profile_enable(int on);
 int sffn_profile_read(float* ms, const char** names, int max_n);
+
+/* Measurement aid (not part of the method): the two element-wise operations of the DENSE FFN step that the benchmark
+ * times as its baseline, each as one pass over HBM: eq. (2) y2 = bf16(max(y1, 0)^2) and eq. (6)
+ * dy1 = bf16(2 * dy2 * max(y1, 0)) of Section 2.1 on n contiguous bf16 elements (n a positive multiple of 8, pointers
+ * 16-byte aligned, device memory; outputs may not alias inputs).  SFFN_EINVAL with nothing enqueued otherwise. */
+int sffn_dense_sqrelu(const uint16_t* y1, uint16_t* y2, int64_t n, void* stream);
+int sffn_dense_dsqrelu(const uint16_t* dy2, const uint16_t* y1, uint16_t* dy1, int64_t n, void* stream);
 
 #ifdef __cplusplus
 }

@@ -14,5 +14,5 @@ from .vnm import (sqrelu, vnm_select_columns, vnm_compress, vnm_decompress,
                   sqrelu_vnm_compress, dsqrelu_vnm, vnm_to_24)
 from .gemm import spmm24, vnm_spmm, vnm_wgrad, dense_nt
 from .ffn import ffn_sparse_step_ref, ffn_dense_ref, ffn_sparse_step_grouped_ref
-from .router import (route_scores, route_top1, expert_permutation, cluster_rows, expert_matmul, venom_from_compact,
+from .router import (route_scores, route_scores_plain, route_margin_is_clear, route_top1, expert_permutation, cluster_rows, expert_matmul, venom_from_compact,
                      moe_to_venom, scatter_compact, ffn_router_step_ref)

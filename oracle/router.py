@@ -32,8 +32,33 @@ from .vnm import sqrelu, vnm_decompress, dsqrelu_vnm
 from .gemm import vnm_spmm, vnm_wgrad, dense_nt
 
 
+def route_scores_plain(x_bits, means_bits):
+    """THE DEFINITION (Section 3.3, step 1; Alg. 3's similarity): s = x @ ExpertMeans, here in float64 through the
+    library matmul, no summation order implied.  route_top1 of it is the expert the paper's rule picks."""
+    return bits_to_f64(np.asarray(x_bits, dtype=np.uint16)) @ bits_to_f64(np.asarray(means_bits, dtype=np.uint16)).T
+
+
+def route_margin_is_clear(x_bits, means_bits):
+    """Per token: does the definition decide the expert whatever the order of the float32 summation?  True where the
+    float64 gap between the best and the second-best score exceeds the sum of the two experts' rounding bounds
+    14 * 2^-24 * sum_d |x||mean| (8 sequential + 6 tree additions of the stated order; any order with as few
+    roundings per term stays inside it)."""
+    x, m = bits_to_f64(np.asarray(x_bits, dtype=np.uint16)), bits_to_f64(np.asarray(means_bits, dtype=np.uint16))
+    s, bound = x @ m.T, 14 * 2.0 ** -24 * (np.abs(x) @ np.abs(m).T)
+    if s.shape[1] < 2:
+        return np.ones(s.shape[0], dtype=bool)
+    order = np.argsort(-s, axis=1, kind="stable")
+    t = np.arange(s.shape[0])
+    e1, e2 = order[:, 0], order[:, 1]
+    return (s[t, e1] - s[t, e2]) > (bound[t, e1] + bound[t, e2])
+
+
 def route_scores(x_bits, means_bits):
-    """s[t, e] in float32, accumulated in the order stated in the module header.  D must be a multiple of 8."""
+    """s[t, e] in float32.  NOT part of the definition but the contract's choice of ONE summation order (the paper fixes
+    none), needed because the score decides an integer: everything from here to the end of this function restates the
+    order given in the module header, so that near-ties resolve identically on both sides.  Away from near-ties the
+    order is immaterial: route_top1(route_scores) == route_top1(route_scores_plain) wherever route_margin_is_clear.
+    D must be a multiple of 8."""
     x = bits_to_f32(np.asarray(x_bits, dtype=np.uint16))
     m = bits_to_f32(np.asarray(means_bits, dtype=np.uint16))
     T, D = x.shape

@@ -82,6 +82,8 @@ def load():
     lib.sffn_router_full_workspace_bytes.restype = sz
     lib.sffn_router_full_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg)]
     lib.ffn_router_full_step.argtypes = [ctypes.POINTER(_Cfg)] + [p] * 10 + [p, sz, p]
+    lib.sffn_dense_sqrelu.argtypes = [p, p, i64, p]
+    lib.sffn_dense_dsqrelu.argtypes = [p, p, p, i64, p]
     lib.sffn_profile_enable.argtypes = [i32]
     lib.sffn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_char_p), i32]
     _LIB = lib
@@ -100,6 +102,25 @@ def _ptr(t, rows_strided=False):
     if not t.is_cuda or not ok:
         raise SffnError("expected a contiguous device tensor")
     return ctypes.c_void_p(t.data_ptr())
+
+
+_BF16 = (torch.bfloat16, torch.int16, torch.uint16)      # bf16 values or their bit patterns
+_U8 = (torch.uint8,)
+_F32 = (torch.float32,)
+_I32 = (torch.int32,)
+
+
+def _want(name, t, shape, kinds, optional=False):
+    """The C ABI sees raw pointers only, so sizes and element types are checked here, before any call: a short or
+    mistyped tensor would otherwise become an out-of-bounds device access inside a kernel."""
+    if t is None:
+        if optional:
+            return
+        raise SffnError("%s: missing tensor" % name)
+    if tuple(t.shape) != tuple(int(v) for v in shape):
+        raise SffnError("%s: expected shape %s, got %s" % (name, tuple(int(v) for v in shape), tuple(t.shape)))
+    if t.dtype not in kinds:
+        raise SffnError("%s: expected dtype %s, got %s" % (name, " / ".join(str(k) for k in kinds), t.dtype))
 
 
 def _stream():
@@ -135,23 +156,40 @@ def profile_read():
 FLAG_KEEP_DENSE = 1
 
 
+def dense_sqrelu(y1, out):
+    """Measurement aid: eq. (2) on a whole tensor in one pass (the dense baseline's element-wise kernel)."""
+    _want("dense_sqrelu: out", out, y1.shape, _BF16)
+    _check(load().sffn_dense_sqrelu(_ptr(y1), _ptr(out), y1.numel(), _stream()))
+    return out
+
+
+def dense_dsqrelu(dy2, y1, out):
+    """Measurement aid: eq. (6) on whole tensors in one pass."""
+    _want("dense_dsqrelu: y1", y1, dy2.shape, _BF16)
+    _want("dense_dsqrelu: out", out, dy2.shape, _BF16)
+    _check(load().sffn_dense_dsqrelu(_ptr(dy2), _ptr(y1), _ptr(out), dy2.numel(), _stream()))
+    return out
+
+
 def _cfg(T, D, F, mode=MODE_HARD, V=64, M=8, flags=0):
     return _Cfg(T, D, F, V, M, mode, flags)
 
 
-def workspace_bytes(T, D, F, mode=MODE_HARD, M=8):
-    c = _cfg(T, D, F, mode, M=M)
+def workspace_bytes(T, D, F, mode=MODE_HARD, M=8, keep_dense=False):
+    c = _cfg(T, D, F, mode, M=M, flags=FLAG_KEEP_DENSE if keep_dense else 0)
     return load().sffn_workspace_bytes(ctypes.byref(c))
 
 
-def workspace_layout(T, D, F, mode=MODE_HARD, M=8):
-    c, lay = _cfg(T, D, F, mode, M=M), _Layout()
+def workspace_layout(T, D, F, mode=MODE_HARD, M=8, keep_dense=False):
+    c, lay = _cfg(T, D, F, mode, M=M, flags=FLAG_KEEP_DENSE if keep_dense else 0), _Layout()
     _check(load().sffn_workspace_layout(ctypes.byref(c), ctypes.byref(lay)))
     return {n: getattr(lay, n) for n, _ in _Layout._fields_}
 
 
 def prune24_compress(src, trans=False, mode=MODE_HARD):
     """src [R, K] (trans=False) or [K, R] (trans=True: groups run down the rows).  -> vals [R, K/2], meta [R, K/8]."""
+    if src is None or src.dim() != 2 or src.dtype not in _BF16:
+        raise SffnError("prune24_compress: src must be a 2-D bf16 tensor")
     rows, cols = src.shape
     R, K = (cols, rows) if trans else (rows, cols)
     vals, meta = _bf16((R, K // 2), src.device), _u8((R, K // 8), src.device)
@@ -160,6 +198,8 @@ def prune24_compress(src, trans=False, mode=MODE_HARD):
 
 
 def sqrelu_vnm_compress(y1, V=64, M=8):
+    if y1 is None or y1.dim() != 2 or y1.dtype not in _BF16:
+        raise SffnError("sqrelu_vnm_compress: y1 must be a 2-D bf16 tensor")
     T, F = y1.shape
     vals, meta = _bf16((T, 2 * F // M), y1.device), _u8((T, F // (2 * M)), y1.device)
     colidx = _u8((T // V, F // M, 4), y1.device)
@@ -168,25 +208,42 @@ def sqrelu_vnm_compress(y1, V=64, M=8):
 
 
 def spmm24_fwd(X, w_vals, w_meta, bias=None):
+    if X is None or X.dim() != 2 or w_vals is None or w_vals.dim() != 2:
+        raise SffnError("spmm24_fwd: X and w_vals must be 2-D tensors")
     T, K = X.shape
     N = w_vals.shape[0]
+    _want("spmm24_fwd: X", X, (T, K), _BF16)
+    _want("spmm24_fwd: w_vals", w_vals, (N, K // 2), _BF16)
+    _want("spmm24_fwd: w_meta", w_meta, (N, K // 8), _U8)
+    _want("spmm24_fwd: bias", bias, (N,), _F32, optional=True)
     out = _bf16((T, N), X.device)
     _check(load().spmm24_fwd(_ptr(X), _ptr(w_vals), _ptr(w_meta), _ptr(bias), T, N, K, _ptr(out), _stream()))
     return out
 
 
 def spmm24_dgrad(dY, wt_vals, wt_meta):
+    if dY is None or dY.dim() != 2 or wt_vals is None or wt_vals.dim() != 2:
+        raise SffnError("spmm24_dgrad: dY and wt_vals must be 2-D tensors")
     T, K = dY.shape
     N = wt_vals.shape[0]
+    _want("spmm24_dgrad: dY", dY, (T, K), _BF16)
+    _want("spmm24_dgrad: wt_vals", wt_vals, (N, K // 2), _BF16)
+    _want("spmm24_dgrad: wt_meta", wt_meta, (N, K // 8), _U8)
     out = _bf16((T, N), dY.device)
     _check(load().spmm24_dgrad(_ptr(dY), _ptr(wt_vals), _ptr(wt_meta), T, N, K, _ptr(out), _stream()))
     return out
 
 
 def vnm_spmm(a_vals, a_meta, a_colidx, Wd, w_kmajor, V=64, M=8):
+    if a_vals is None or a_vals.dim() != 2 or Wd is None or Wd.dim() != 2:
+        raise SffnError("vnm_spmm: a_vals and Wd must be 2-D tensors")
     T = a_vals.shape[0]
     Kfull = a_vals.shape[1] * M // 2
     N = Wd.shape[1] if w_kmajor else Wd.shape[0]
+    _want("vnm_spmm: a_vals", a_vals, (T, 2 * Kfull // M), _BF16)
+    _want("vnm_spmm: a_meta", a_meta, (T, Kfull // (2 * M)), _U8)
+    _want("vnm_spmm: a_colidx", a_colidx, (T // V, Kfull // M, 4), _U8)
+    _want("vnm_spmm: Wd", Wd, (Kfull, N) if w_kmajor else (N, Kfull), _BF16)
     out = _bf16((T, N), a_vals.device)
     nbytes = load().sffn_vnm_spmm_workspace_bytes(T, N, Kfull, int(w_kmajor))
     ws = _u8((max(nbytes, 16),), a_vals.device)
@@ -196,15 +253,27 @@ def vnm_spmm(a_vals, a_meta, a_colidx, Wd, w_kmajor, V=64, M=8):
 
 
 def dsqrelu_vnm(dy2, y1, meta, colidx, V=64, M=8):
+    if y1 is None or y1.dim() != 2:
+        raise SffnError("dsqrelu_vnm: y1 must be a 2-D tensor")
     T, F = y1.shape
+    _want("dsqrelu_vnm: y1", y1, (T, F), _BF16)
+    _want("dsqrelu_vnm: dy2", dy2, (T, F), _BF16)
+    _want("dsqrelu_vnm: meta", meta, (T, F // (2 * M)), _U8)
+    _want("dsqrelu_vnm: colidx", colidx, (T // V, F // M, 4), _U8)
     dvals = _bf16((T, 2 * F // M), y1.device)
     _check(load().dsqrelu_vnm(_ptr(dy2), _ptr(y1), _ptr(meta), _ptr(colidx), T, F, V, M, _ptr(dvals), _stream()))
     return dvals
 
 
 def vnm_wgrad(a_vals, a_meta, a_colidx, G, out_f_major, V=64, M=8):
+    if G is None or G.dim() != 2 or a_vals is None or a_vals.dim() != 2:
+        raise SffnError("vnm_wgrad: G and a_vals must be 2-D tensors")
     T, N = G.shape
     F = a_vals.shape[1] * M // 2
+    _want("vnm_wgrad: G", G, (T, N), _BF16)
+    _want("vnm_wgrad: a_vals", a_vals, (T, 2 * F // M), _BF16)
+    _want("vnm_wgrad: a_meta", a_meta, (T, F // (2 * M)), _U8)
+    _want("vnm_wgrad: a_colidx", a_colidx, (T // V, F // M, 4), _U8)
     out = _bf16((F, N) if out_f_major else (N, F), G.device)
     nbytes = load().sffn_vnm_wgrad_workspace_bytes(T, F, N)
     ws = _u8((max(nbytes, 16),), G.device)
@@ -222,12 +291,18 @@ class FfnStep:
         path that always stores y1 and dy2 and produces no y1_kept)."""
         self.T, self.D, self.F, self.mode, self.keep_dense, self.M = T, D, F, mode, keep_dense, M
         self.cfg = _cfg(T, D, F, mode, M=M, flags=FLAG_KEEP_DENSE if keep_dense else 0)
-        self.layout = workspace_layout(T, D, F, mode, M)
+        self.layout = workspace_layout(T, D, F, mode, M, keep_dense)
         self.ws = _u8((self.layout["total"],), device)
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
         self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
 
     def __call__(self, X, W1, W2, b1, dY):
+        T, D, F = self.T, self.D, self.F
+        _want("ffn_sparse_step: X", X, (T, D), _BF16)
+        _want("ffn_sparse_step: W1", W1, (F, D), _BF16)
+        _want("ffn_sparse_step: W2", W2, (D, F), _BF16)
+        _want("ffn_sparse_step: b1", b1, (F,), _F32, optional=True)
+        _want("ffn_sparse_step: dY", dY, (T, D), _BF16)
         _check(load().ffn_sparse_step(ctypes.byref(self.cfg), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY), _ptr(self.Y3),
                                       _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
@@ -245,9 +320,11 @@ class FfnStep:
 
         out = dict(w1_vals=view(L["w1_vals"], (F, D // 2), torch.bfloat16), w1_meta=view(L["w1_meta"], (F, D // 8), torch.uint8),
                    w2t_vals=view(L["w2t_vals"], (F, D // 2), torch.bfloat16), w2t_meta=view(L["w2t_meta"], (F, D // 8), torch.uint8),
-                   y1=view(L["y1"], (T, F), torch.bfloat16), y2_vals=view(L["y2_vals"], (T, 2 * F // M), torch.bfloat16),
+                   y2_vals=view(L["y2_vals"], (T, 2 * F // M), torch.bfloat16),
                    y2_meta=view(L["y2_meta"], (T, F // (2 * M)), torch.uint8), colidx=view(L["colidx"], (T // 64, F // M, 4), torch.uint8),
-                   dy2=view(L["dy2"], (T, F), torch.bfloat16), dy1_vals=view(L["dy1_vals"], (T, 2 * F // M), torch.bfloat16))
+                   dy1_vals=view(L["dy1_vals"], (T, 2 * F // M), torch.bfloat16))
+        if self.keep_dense or M != 8:       # the dense y1 / dy2 have room in the workspace only when they are stored
+            out["y1"], out["dy2"] = view(L["y1"], (T, F), torch.bfloat16), view(L["dy2"], (T, F), torch.bfloat16)
         if M == 8:
             out["y1_kept"] = view(L["y1_kept"], (T, F // 4), torch.bfloat16)
         return out
@@ -259,7 +336,7 @@ class FfnStepGrouped:
 
     def __init__(self, seg, D, F, mode=MODE_HARD, device="cuda", keep_dense=False):
         self.seg = [int(v) for v in seg]
-        self.E, self.T, self.D, self.F, self.mode = len(self.seg) - 1, self.seg[-1], D, F, mode
+        self.E, self.T, self.D, self.F, self.mode, self.keep_dense = len(self.seg) - 1, self.seg[-1], D, F, mode, keep_dense
         self.seg_c = (ctypes.c_int64 * len(self.seg))(*self.seg)
         self.cfg = _cfg(self.T, D, F, mode, flags=FLAG_KEEP_DENSE if keep_dense else 0)
         lay = _Layout()
@@ -270,6 +347,12 @@ class FfnStepGrouped:
         self.dW1, self.dW2 = _bf16((self.E, F, D), device), _bf16((self.E, D, F), device)
 
     def __call__(self, X, W1, W2, b1, dY):
+        T, D, F, E = self.T, self.D, self.F, self.E
+        _want("ffn_sparse_step_grouped: X", X, (T, D), _BF16)
+        _want("ffn_sparse_step_grouped: W1", W1, (E, F, D), _BF16)
+        _want("ffn_sparse_step_grouped: W2", W2, (E, D, F), _BF16)
+        _want("ffn_sparse_step_grouped: b1", b1, (E, F), _F32, optional=True)
+        _want("ffn_sparse_step_grouped: dY", dY, (T, D), _BF16)
         _check(load().ffn_sparse_step_grouped(ctypes.byref(self.cfg), self.E, self.seg_c, _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1),
                                               _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws),
                                               self.layout["total"], _stream()))
@@ -286,12 +369,15 @@ class FfnStepGrouped:
             nbytes = n * (2 if dtype == torch.bfloat16 else 1)
             return self.ws[off:off + nbytes].view(dtype).view(shape)
 
-        return dict(w1_vals=view(L["w1_vals"], (E, F, D // 2), torch.bfloat16), w1_meta=view(L["w1_meta"], (E, F, D // 8), torch.uint8),
-                    w2t_vals=view(L["w2t_vals"], (E, F, D // 2), torch.bfloat16), w2t_meta=view(L["w2t_meta"], (E, F, D // 8), torch.uint8),
-                    y1=view(L["y1"], (T, F), torch.bfloat16), y2_vals=view(L["y2_vals"], (T, F // 4), torch.bfloat16),
-                    y2_meta=view(L["y2_meta"], (T, F // 16), torch.uint8), colidx=view(L["colidx"], (T // 64, F // 8, 4), torch.uint8),
-                    dy2=view(L["dy2"], (T, F), torch.bfloat16), dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16),
-                    y1_kept=view(L["y1_kept"], (T, F // 4), torch.bfloat16))
+        out = dict(w1_vals=view(L["w1_vals"], (E, F, D // 2), torch.bfloat16), w1_meta=view(L["w1_meta"], (E, F, D // 8), torch.uint8),
+                   w2t_vals=view(L["w2t_vals"], (E, F, D // 2), torch.bfloat16), w2t_meta=view(L["w2t_meta"], (E, F, D // 8), torch.uint8),
+                   y2_vals=view(L["y2_vals"], (T, F // 4), torch.bfloat16),
+                   y2_meta=view(L["y2_meta"], (T, F // 16), torch.uint8), colidx=view(L["colidx"], (T // 64, F // 8, 4), torch.uint8),
+                   dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16),
+                   y1_kept=view(L["y1_kept"], (T, F // 4), torch.bfloat16))
+        if self.keep_dense:
+            out["y1"], out["dy2"] = view(L["y1"], (T, F), torch.bfloat16), view(L["dy2"], (T, F), torch.bfloat16)
+        return out
 
 
 def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD, keep_dense=True, M=8):
@@ -304,8 +390,12 @@ def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD, keep_dense=True, M=8):
 
 def venom_route_launch(X, means, M, want_scores=False):
     """venom_route without the read-back: seg stays a device tensor (int32, first M/4 + 1 entries)."""
+    if X is None or X.dim() != 2:
+        raise SffnError("venom_route: X must be a 2-D tensor")
     T, D = X.shape
     E = M // 4
+    _want("venom_route: X", X, (T, D), _BF16)
+    _want("venom_route: means", means, (E, D), _BF16)
     rows = load().sffn_venom_rows(T, M)
     dev = X.device
     i32t = lambda n: torch.empty((n,), dtype=torch.int32, device=dev)
@@ -330,10 +420,18 @@ def venom_route(X, means, M, want_scores=False):
 def venom_expert_matmul(X, perm, seg, W1, b1, M, mode=MODE_HARD, keep_y1c=True, workspace=None):
     """Step 3 of Section 3.3: the grouped matmul that emits V:N:M.  -> (vals, meta, colidx, y1c or None) over
     sffn_venom_rows(T, M) rows."""
+    if X is None or X.dim() != 2 or W1 is None or W1.dim() != 2:
+        raise SffnError("venom_expert_matmul: X and W1 must be 2-D tensors")
     T, D = X.shape
     F = W1.shape[0]
     E = M // 4
     rows = load().sffn_venom_rows(T, M)
+    _want("venom_expert_matmul: X", X, (T, D), _BF16)
+    _want("venom_expert_matmul: W1", W1, (F, D), _BF16)
+    _want("venom_expert_matmul: b1", b1, (F,), _F32, optional=True)
+    _want("venom_expert_matmul: perm", perm, (rows,), _I32)
+    if len(seg) != E + 1:
+        raise SffnError("venom_expert_matmul: seg must hold M / 4 + 1 run offsets")
     dev = X.device
     vals, meta = _bf16((rows, 2 * F // M), dev), _u8((rows, F // (2 * M)), dev)
     colidx = _u8((rows // 64, F // M, 4), dev)
@@ -371,9 +469,21 @@ class FfnRouterStep:
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
         self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
 
+    def _want_inputs(self, who, X, W1, W2, b1, dY):
+        T, D, F = self.T, self.D, self.F
+        _want(who + ": X", X, (T, D), _BF16)
+        _want(who + ": W1", W1, (F, D), _BF16)
+        _want(who + ": W2", W2, (D, F), _BF16)
+        _want(who + ": b1", b1, (F,), _F32, optional=True)
+        _want(who + ": dY", dY, (T, D), _BF16)
+
     def __call__(self, route, X, W1, W2, b1, dY):
         """route: the dict venom_route returned for X."""
         E = self.M // 4
+        self._want_inputs("ffn_router_step", X, W1, W2, b1, dY)
+        _want("ffn_router_step: perm", route["perm"], (self.rows,), _I32)
+        if len(route["seg"]) != E + 1:
+            raise SffnError("ffn_router_step: seg must hold M / 4 + 1 run offsets")
         seg_arr = (ctypes.c_int64 * (E + 1))(*[int(v) for v in route["seg"]])
         _check(load().ffn_router_step(ctypes.byref(self.cfg), seg_arr, _ptr(route["perm"]), _ptr(X), _ptr(W1),
                                       _ptr(W2), _ptr(b1), _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2),
@@ -382,6 +492,8 @@ class FfnRouterStep:
 
     def full(self, means, X, W1, W2, b1, dY):
         """Routing included (ffn_router_full_step): no read-back of the run offsets, nothing but launches on the stream."""
+        self._want_inputs("ffn_router_full_step", X, W1, W2, b1, dY)
+        _want("ffn_router_full_step: means", means, (self.M // 4, self.D), _BF16)
         _check(load().ffn_router_full_step(ctypes.byref(self.cfg), _ptr(means), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY),
                                            _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.ws_bytes, _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2

@@ -50,17 +50,20 @@ struct FullLayout {
 // E = number of experts (1 for the plain step): every weight-shaped tensor holds E matrices back to back.
 bool make_layout(const sffn_cfg* c, FullLayout* L, int n_experts = 1) {
     if (!c || !mult64(c->T) || !mult64(c->D) || !mult64(c->F) || n_experts < 1) return false;
-    const size_t M = (c->M == 16 || c->M == 32 || c->M == 64) ? (size_t)c->M : 8;   // wider blocks: smaller packed tensors, unfused path
+    if (!vnm_ok(c->V, c->M)) return false;
+    const size_t M = (size_t)c->M;                                    // wider blocks: smaller packed tensors, unfused path
     if (c->F % (2 * M) != 0) return false;
+    // the dense y1 / dy2 exist only where a kernel stores them: on request in the fused M = 8 step, always in the unfused one
+    const bool dense = (c->flags & SFFN_FLAG_KEEP_DENSE) || M != 8;
     const size_t T = c->T, D = c->D, F = (size_t)c->F * n_experts;   // F only sizes weight-shaped tensors below ...
     const size_t TF = T * (size_t)c->F;                               // ... token x hidden tensors use TF
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
     L->pub.w1_vals = take(F * D);          L->pub.w1_meta = take(F * D / 8);
     L->pub.w2t_vals = take(F * D);         L->pub.w2t_meta = take(F * D / 8);
-    L->pub.y1 = take(TF * 2);
+    L->pub.y1 = take(dense ? TF * 2 : 0);
     L->pub.y2_vals = take(TF * 4 / M);  L->pub.y2_meta = take(TF / (2 * M));   L->pub.colidx = take(TF / 64 / M * 4);
-    L->pub.dy2 = take(TF * 2);
+    L->pub.dy2 = take(dense ? TF * 2 : 0);
     L->pub.dy1_vals = take(TF * 4 / M);
     L->pub.y1_kept = take(M == 8 ? TF / 2 : 0);
     L->w1_vblk = take(F * D);              L->w1_mblk = take(F * D / 8);
@@ -91,7 +94,7 @@ size_t sffn_workspace_bytes(const sffn_cfg* cfg) {
 int sffn_workspace_layout(const sffn_cfg* cfg, sffn_ws_layout* out) {
     FullLayout L;
     REQUIRE(out != nullptr, SFFN_EINVAL, "sffn_workspace_layout: out is null");
-    REQUIRE(make_layout(cfg, &L), SFFN_EINVAL, "sffn_workspace_layout: T, D, F must be positive multiples of 64");
+    REQUIRE(make_layout(cfg, &L), SFFN_EINVAL, "sffn_workspace_layout: T, D, F must be positive multiples of 64, V = 64, M in {8, 16, 32, 64}, F a multiple of 2 M");
     *out = L.pub;
     return SFFN_OK;
 }
@@ -186,6 +189,7 @@ int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_col
         LAUNCH(launch_vnm_spmm_gather(a_vals, a_meta, a_colidx, W, ldk, T, N, Kfull, M, out, N, s), "vnm_spmm/gather");
         return SFFN_OK;
     }
+    REQUIRE(T < 65536, SFFN_EUNSUPPORTED, "vnm_spmm: T must be below 65536 on the plain-2:4 route (shapes the gathered-row kernel does not cover)");
     if (M == 8) LAUNCH(launch_vnm_to_24(a_vals, a_meta, a_colidx, T, Kfull, v24, m24, s), "vnm_spmm/to24");
     else        LAUNCH(launch_vnm_to_24_m(a_vals, a_meta, a_colidx, T, Kfull, M, v24, m24, s), "vnm_spmm/to24");
     if (w_kmajor) {
@@ -364,7 +368,7 @@ int sffn_router_workspace_layout(const sffn_cfg* cfg, sffn_router_layout* out) {
 // or as a device array written earlier on the same stream by this library's own grouping kernels (seg_dev).
 static int run_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* seg_dev, const int32_t* perm, const uint16_t* X,
                            const uint16_t* W1, const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX,
-                           uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
+                           uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream, bool check_only = false) {
     REQUIRE(cfg && (seg_offsets || seg_dev) && perm && X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_router_step: null pointer");
     REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "ffn_router_step: only V=64 with M in {8, 16, 32, 64} is built");
     RouterLayout L;
@@ -398,6 +402,7 @@ static int run_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, cons
     const int logM = M == 8 ? 3 : M == 16 ? 4 : M == 32 ? 5 : 6;
     g2.map_logM = logM;
     const int64_t used = seg_dev ? 0 : seg_offsets[E];   // (device table: the end of the last run is only known on the device)
+    if (check_only) return SFFN_OK;                      // every argument check is above this line, every launch below it
 
     hipStream_t s = (hipStream_t)stream;
     unsigned char* ws = (unsigned char*)workspace;
@@ -500,6 +505,9 @@ int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint1
     int32_t* expert = (int32_t*)(ws + A.expert);
     int32_t* perm = (int32_t*)(ws + A.perm);
     int32_t* seg = (int32_t*)(ws + A.seg);
+    // the step's own argument checks run first, so that a rejected call leaves nothing on the stream
+    const int pre = run_router_step(cfg, nullptr, seg, perm, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, L.total, stream, true);
+    if (pre != SFFN_OK) return pre;
     const int rc = venom_route(X, means, cfg->T, cfg->D, cfg->M, expert, perm, (int32_t*)(ws + A.row_of_token), seg, nullptr, ws + A.counts,
                                A.total - A.counts, stream);
     if (rc != SFFN_OK) return rc;
@@ -660,7 +668,7 @@ size_t sffn_grouped_workspace_bytes(const sffn_cfg* cfg, int n_experts) {
 int sffn_grouped_workspace_layout(const sffn_cfg* cfg, int n_experts, sffn_ws_layout* out) {
     FullLayout L;
     REQUIRE(out != nullptr, SFFN_EINVAL, "sffn_grouped_workspace_layout: out is null");
-    REQUIRE(make_layout(cfg, &L, n_experts), SFFN_EINVAL, "sffn_grouped_workspace_layout: T, D, F must be positive multiples of 64, n_experts >= 1");
+    REQUIRE(make_layout(cfg, &L, n_experts), SFFN_EINVAL, "sffn_grouped_workspace_layout: T, D, F must be positive multiples of 64, V = 64, M in {8, 16, 32, 64}, n_experts >= 1");
     *out = L.pub;
     return SFFN_OK;
 }

@@ -128,6 +128,84 @@ def test_router_entry_points_validate_on_the_host():
     assert lib.ffn_router_full_step(ctypes.byref(m12), *args, fake, big, None) == -2
 
 
+def test_workspace_has_no_dense_activation_unless_it_is_stored():
+    """Without SFFN_FLAG_KEEP_DENSE the fused M = 8 step never writes the dense y1 / dy2, and its workspace has no room for
+    them: exactly 2 x 2 T F bytes smaller.  The unfused wide-block path always stores them.  Unknown M: no layout."""
+    T, D, F = 512, 256, 1024
+    small, big = sffn.workspace_bytes(T, D, F), sffn.workspace_bytes(T, D, F, keep_dense=True)
+    assert big - small == 2 * 2 * T * F
+    lay = sffn.workspace_layout(T, D, F)
+    assert lay["y2_vals"] == lay["y1"] and lay["dy1_vals"] == lay["dy2"]            # empty regions
+    layk = sffn.workspace_layout(T, D, F, keep_dense=True)
+    assert layk["y2_vals"] - layk["y1"] == 2 * T * F and layk["dy1_vals"] - layk["dy2"] == 2 * T * F
+    assert sffn.workspace_bytes(T, D, F, M=16) == sffn.workspace_bytes(T, D, F, M=16, keep_dense=True) > 0
+    lib = sffn.load()
+    for M in (0, 4, 12, 128):
+        c = binding._Cfg(T, D, F, 64, M, 0, 0)
+        assert lib.sffn_workspace_bytes(ctypes.byref(c)) == 0
+        assert lib.sffn_workspace_layout(ctypes.byref(c), ctypes.byref(binding._Layout())) == -1
+        assert lib.ffn_sparse_step(ctypes.byref(c), *([ctypes.c_void_p(0x1000)] * 9), ctypes.c_void_p(0x1000), 1 << 40, None) == -2
+    c = binding._Cfg(T, D, F, 32, 8, 0, 0)
+    assert lib.sffn_workspace_bytes(ctypes.byref(c)) == 0
+
+
+def test_binding_rejects_mismatched_tensors_before_any_call(monkeypatch):
+    """The binding is the only layer that knows tensor sizes: a wrong shape or element type must raise before the C
+    entry point is reached (checked here by making every entry point unreachable), for every wrapper that takes tensors."""
+    import torch
+
+    class Unreachable:
+        def __getattr__(self, name):
+            if name.startswith("sffn_") and ("bytes" in name or "rows" in name or "layout" in name):
+                return getattr(real, name)
+
+            def reached(*a):
+                raise AssertionError("C entry point %s reached" % name)
+            return reached
+    real = sffn.load()
+    bf, u8, f32, i32 = torch.bfloat16, torch.uint8, torch.float32, torch.int32
+    z = lambda shape, dt=bf: torch.zeros(shape, dtype=dt)
+    T, D, F, M = 128, 64, 256, 8
+    step = sffn.FfnStep.__new__(sffn.FfnStep)
+    step.T, step.D, step.F, step.M, step.mode, step.keep_dense = T, D, F, M, 0, False
+    step.cfg = binding._cfg(T, D, F)
+    grouped = sffn.FfnStepGrouped.__new__(sffn.FfnStepGrouped)
+    grouped.T, grouped.D, grouped.F, grouped.E = T, D, F, 2
+    router = sffn.FfnRouterStep.__new__(sffn.FfnRouterStep)
+    router.T, router.D, router.F, router.M, router.rows = T, D, F, 16, real.sffn_venom_rows(T, 16)
+    monkeypatch.setattr(binding, "_LIB", Unreachable())
+    good = dict(X=z((T, D)), W1=z((F, D)), W2=z((D, F)), b1=z((F,), f32), dY=z((T, D)))
+    cases = [
+        lambda: step(z((T - 64, D)), good["W1"], good["W2"], good["b1"], good["dY"]),              # short X
+        lambda: step(good["X"], good["W1"], good["W2"], z((F,), bf), good["dY"]),                   # bf16 bias where fp32 is read
+        lambda: step(good["X"], z((F, D), f32), good["W2"], good["b1"], good["dY"]),                # fp32 weights
+        lambda: step(good["X"], good["W1"], z((F, D)), good["b1"], good["dY"]),                     # W2 transposed
+        lambda: step(good["X"], good["W1"], good["W2"], good["b1"], z((T, D + 64))),
+        lambda: grouped(good["X"], z((1, F, D)), z((2, D, F)), None, good["dY"]),
+        lambda: grouped(good["X"], z((2, F, D)), z((2, D, F)), z((F,), f32), good["dY"]),
+        lambda: router.full(z((3, D)), good["X"], good["W1"], good["W2"], good["b1"], good["dY"]),   # M / 4 = 4 means wanted
+        lambda: router(dict(perm=z((router.rows - 1,), i32), seg=[0] * 5), good["X"], good["W1"], good["W2"], good["b1"], good["dY"]),
+        lambda: router(dict(perm=z((router.rows,), i32), seg=[0] * 4), good["X"], good["W1"], good["W2"], good["b1"], good["dY"]),
+        lambda: sffn.spmm24_fwd(good["X"], z((F, D // 2 - 8)), z((F, D // 8), u8)),                # w_vals narrower than K / 2
+        lambda: sffn.spmm24_fwd(good["X"], z((F, D // 2)), z((F, D // 8), u8), z((F,), bf)),
+        lambda: sffn.spmm24_dgrad(good["dY"], z((F, D // 2)), z((F, D // 8), i32)),
+        lambda: sffn.vnm_spmm(z((T, F // 4)), z((T, F // 16), u8), z((T // 64, F // 8, 3), u8), good["W1"], 1),
+        lambda: sffn.vnm_spmm(z((T, F // 4)), z((T, F // 16), u8), z((T // 64, F // 8, 4), u8), good["W1"], 0),   # W given in the other orientation
+        lambda: sffn.dsqrelu_vnm(z((T, F)), z((T + 64, F)), z((T, F // 16), u8), z((T // 64, F // 8, 4), u8)),
+        lambda: sffn.vnm_wgrad(z((T, F // 4)), z((T, F // 16), u8), z((T // 64, F // 8, 4), u8), z((T // 2, D)), 1),
+        lambda: sffn.venom_route_launch(good["X"], z((2, D)), 16),
+        lambda: sffn.venom_expert_matmul(good["X"], z((router.rows,), torch.int64), [0] * 5, good["W1"], good["b1"], 16),
+        lambda: sffn.prune24_compress(z((F, D), f32)),
+        lambda: sffn.sqrelu_vnm_compress(z((T, F), u8)),
+    ]
+    for n, case in enumerate(cases):
+        with pytest.raises(sffn.SffnError):
+            case()
+    # and matching host tensors get as far as the device check, still without a call
+    with pytest.raises(sffn.SffnError, match="device"):
+        step(**good)
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB", None)
     monkeypatch.setattr(binding, "_HERE", str(tmp_path))

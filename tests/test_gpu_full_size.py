@@ -8,14 +8,14 @@ import torch
 
 import oracle
 import paper_2602_06183_amd as sffn
-from tests.util import to_dev, to_bits, assert_gemm_close
-from workload import CONFIGS, make_ffn_inputs, make_moe_inputs
+from tests.util import to_dev, to_bits, assert_gemm_close, assert_routing_matches_the_definition
+from workload import CONFIGS, make_ffn_inputs, make_ffn_sweep, make_moe_inputs
 
 pytestmark = pytest.mark.gpu
 
 
-def _run(dev, T, D, F, keep):
-    step = sffn.FfnStep(T, D, F, sffn.MODE_HARD, keep_dense=keep)
+def _run(dev, T, D, F, keep, mode=sffn.MODE_HARD):
+    step = sffn.FfnStep(T, D, F, mode, keep_dense=keep)
     outs = step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
     torch.cuda.synchronize()
     return step, outs
@@ -30,22 +30,48 @@ def test_full_size_step(name, tb_slices):
     T, D, F = CONFIGS[name]
     inp = make_ffn_inputs(T, D, F, seed=0)
     dev = {k: to_dev(v) for k, v in inp.items()}
+    _both_configurations_then_sampled_check(inp, dev, T, D, F, tb_slices)
 
-    step0, outs0 = _run(dev, T, D, F, keep=False)              # what bench.py times
+
+def _both_configurations_then_sampled_check(inp, dev, T, D, F, tb_slices, mode=sffn.MODE_HARD, zero_fraction=0.90):
+    step0, outs0 = _run(dev, T, D, F, keep=False, mode=mode)   # what bench.py times
     fast = [to_bits(t).copy() for t in outs0] + [to_bits(step0.saved()[k]).copy() for k in PACKED_KEYS]
     del step0, outs0
     torch.cuda.empty_cache()
-    step, outs = _run(dev, T, D, F, keep=True)
+    step, outs = _run(dev, T, D, F, keep=True, mode=mode)
     sv = step.saved()
     full = [to_bits(t) for t in outs] + [to_bits(sv[k]) for k in PACKED_KEYS]
     for a, b in zip(fast, full):
         assert np.array_equal(a, b)
     del fast
-    _sampled_step_check(inp, full, to_bits(sv["y1"]), to_bits(sv["dy2"]), tb_slices)
+    _sampled_step_check(inp, full, to_bits(sv["y1"]), to_bits(sv["dy2"]), tb_slices, mode, zero_fraction)
 
 
-def _sampled_step_check(inp, full, y1, dy2, tb_slices):
-    """inp: X, W1, W2, b1, dY of ONE FFN; full: its Y3, dX, dW1, dW2 followed by the PACKED_KEYS tensors."""
+def test_full_size_step_zero_fraction_sweep():
+    """configs[3]: the 70B-scale layer at the other three points of the ReLU zero-fraction sweep (0.90 is the case
+    above): the same inputs with the bias shifted, the timed configuration bit-identical to the checked one, then the
+    same sampled teacher-forced comparison with the oracle, including the zero fraction the bias is meant to give."""
+    T, D, F = CONFIGS["70b"]
+    dev = None
+    for zf, inp in make_ffn_sweep(T, D, F, [0.50, 0.75, 0.95], seed=0):
+        print("70b, zero fraction %.2f" % zf, flush=True)
+        if dev is None:
+            dev = {k: to_dev(v) for k, v in inp.items()}
+        dev["b1"] = to_dev(inp["b1"])
+        _both_configurations_then_sampled_check(inp, dev, T, D, F, [(0, 1), (77, 78)], zero_fraction=zf)
+
+
+def test_full_size_step_soft_threshold():
+    """The paper's own sparsify24 (Section 2.2, soft-thresholding) at the 1B shape, in the timed configuration."""
+    T, D, F = CONFIGS["1b"]
+    inp = make_ffn_inputs(T, D, F, seed=0)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    _both_configurations_then_sampled_check(inp, dev, T, D, F, [(0, 4), (64, 66), (127, 128)], mode=sffn.MODE_SOFT, zero_fraction=None)
+
+
+def _sampled_step_check(inp, full, y1, dy2, tb_slices, mode=sffn.MODE_HARD, zero_fraction=0.90):
+    """inp: X, W1, W2, b1, dY of ONE FFN; full: its Y3, dX, dW1, dW2 followed by the PACKED_KEYS tensors.
+    zero_fraction: what the bias shift is meant to give (None: not checked, e.g. soft-thresholded weights shrink y1's scale)."""
     T, D = inp["X"].shape
     F = inp["W1"].shape[0]
     Y3, dX, dW1, dW2 = full[:4]
@@ -54,9 +80,9 @@ def _sampled_step_check(inp, full, y1, dy2, tb_slices):
 
     # 2:4 weights: bit-exact, everywhere at 1b, on two bands of 1024 rows at the larger shapes (rows are independent)
     for r in ([slice(0, F)] if tb_slices is None else [slice(0, 1024), slice(F - 1024, F)]):
-        rv, rm = oracle.prune24_compress(inp["W1"][r])
+        rv, rm = oracle.prune24_compress(inp["W1"][r], mode)
         assert np.array_equal(w1v[r], rv) and np.array_equal(w1m[r], rm)
-        rv, rm = oracle.prune24_compress(np.ascontiguousarray(inp["W2"][:, r].T))
+        rv, rm = oracle.prune24_compress(np.ascontiguousarray(inp["W2"][:, r].T), mode)
         assert np.array_equal(w2v[r], rv) and np.array_equal(w2m[r], rm)
     del rv, rm
 
@@ -72,8 +98,9 @@ def _sampled_step_check(inp, full, y1, dy2, tb_slices):
         ov, om, oc = oracle.sqrelu_vnm_compress(y1[r])
         assert np.array_equal(yc[b0:b1], oc) and np.array_equal(ym[r], om) and np.array_equal(yv[r], ov)
         assert np.array_equal(dv[r], oracle.dsqrelu_vnm(dy2[r], y1[r], om, oc))
-    zero_frac = float(np.mean(oracle.sqrelu(y1[:2048]) == 0))
-    assert abs(zero_frac - 0.9) < 0.01
+    if zero_fraction is not None:
+        zero_frac = float(np.mean(oracle.sqrelu(y1[:2048]) == 0))
+        assert abs(zero_frac - zero_fraction) < 0.01, (zero_frac, zero_fraction)
 
     # eq. (3), (7): sampled token rows (a row only needs its own 64-token block's column indices)
     def dense_rows(vals, rws):
@@ -205,7 +232,7 @@ def test_full_size_wide_block_step(M):
             assert_gemm_close(got, oracle.f64_to_bits(a.T @ oracle.bits_to_f64(G)), "wgrad columns")
 
 
-@pytest.mark.parametrize("M", [8, 32])
+@pytest.mark.parametrize("M", [8, 16, 32, 64])
 def test_full_size_router(M):
     """Alg. 3 at the 1B shape: routing and grouping bit-exact in full; the grouped matmul on sampled rows; eq. (2) + 2:4
     packing bit-exact on sampled 64-row blocks from the GPU's own y1c; eq. (3) on the result on sampled rows."""
@@ -219,6 +246,7 @@ def test_full_size_router(M):
     expert = oracle.route_top1(oracle.route_scores(inp["X"], inp["means"]))
     perm, seg = oracle.expert_permutation(expert, M // 4)
     assert np.array_equal(to_bits(r["expert"]), expert) and np.array_equal(to_bits(r["perm"]), perm) and r["seg"] == [int(v) for v in seg]
+    assert_routing_matches_the_definition(to_bits(r["expert"]), inp["X"], inp["means"])
     counts = np.bincount(expert, minlength=M // 4)
     assert counts.min() > 0 and counts.max() < 3 * T // (M // 4)          # uneven but not degenerate
     y1c, vals, meta, colidx, y3 = (to_bits(t) for t in (r["y1c"], r["vals"], r["meta"], r["colidx"], y3))

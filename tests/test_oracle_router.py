@@ -67,6 +67,23 @@ def test_route_top1_brute_force_ties_and_cosine():
     assert clear.sum() > 128 and np.array_equal(got[clear], np.argmax(cos, axis=1)[clear])
 
 
+def test_stated_order_agrees_with_the_plain_definition_on_clear_margins():
+    """Section 3.3 step 1 is x @ ExpertMeans; the stated float32 order only settles near-ties.  Wherever the float64 gap
+    between the two best experts exceeds the rounding bound of both scores, the ordered float32 argmax must be the
+    definition's, and such tokens must be the overwhelming majority on the router workload."""
+    for T, D, M, seed in ((700, 256, 8, 1), (1500, 1024, 32, 2), (900, 520, 64, 3)):
+        inp = make_router_inputs(T, D, 256, M, seed=seed)
+        clear = oracle.route_margin_is_clear(inp["X"], inp["means"])
+        plain = oracle.route_top1(oracle.route_scores_plain(inp["X"], inp["means"]))
+        got = oracle.route_top1(oracle.route_scores(inp["X"], inp["means"]))
+        assert clear.mean() > 0.99 and np.array_equal(got[clear], plain[clear])
+    # a constructed near-tie: the definition's gap is below the bound, so the token is reported as undecided
+    x = bf(np.ones((1, 64)))
+    m = bf(np.stack([np.full(64, 0.5), np.full(64, 0.5)]))
+    assert not oracle.route_margin_is_clear(x, m)[0]
+    assert oracle.route_margin_is_clear(x, bf(np.stack([np.full(64, 0.5), np.full(64, 0.25)])))[0]
+
+
 @pytest.mark.parametrize("T,E", [(0, 2), (1, 2), (200, 4), (777, 16), (640, 8)])
 def test_expert_permutation_properties(T, E):
     rng = np.random.default_rng(T + E)

@@ -31,6 +31,28 @@ def _bits_to_f64(b):
     return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
 
+def neuron_std(W1):
+    """Standard deviation of every neuron's pre-activation under X ~ N(0, 1) once the two smallest magnitudes of every
+    four consecutive weights are dropped: the root of the sum, over groups, of the two largest squares (float64).
+    (Closed form of the workload's statistics, not the sparsifier: no positions, no packing, no tie rule.)"""
+    F, D = W1.shape
+    out = np.empty(F, dtype=np.float64)
+    step = max(1, (1 << 24) // D)
+    for r in range(0, F, step):                   # row chunks keep the float64 temporaries small
+        q = _bits_to_f64(W1[r:r + step]) ** 2
+        a, b, c, d = q[:, 0::4], q[:, 1::4], q[:, 2::4], q[:, 3::4]
+        hi1, lo1, hi2, lo2 = np.maximum(a, b), np.minimum(a, b), np.maximum(c, d), np.minimum(c, d)
+        top = np.stack([np.maximum(np.minimum(hi1, hi2), np.maximum(lo1, lo2)), np.maximum(hi1, hi2)], axis=-1)   # 2nd largest, largest
+        out[r:r + step] = np.sqrt(top.sum(axis=(1, 2)))
+    return out
+
+
+def bias_for_zero_fraction(std, zero_fraction):
+    """b1 [F] float32 = -z * std with z the standard-normal quantile of the wanted SquaredReLU zero fraction."""
+    z = Z_FOR_ZERO_FRACTION[zero_fraction] if zero_fraction in Z_FOR_ZERO_FRACTION else float(zero_fraction)
+    return (-z * std).astype(np.float32)
+
+
 def make_ffn_inputs(T, D, F, seed=0, zero_fraction=0.90, w_std=0.02):
     """X [T, D] ~ N(0,1), W1 [F, D] and W2 [D, F] ~ N(0, w_std^2), dY [T, D] ~ N(0,1), all bf16 bits;
     b1 [F] float32 = -z * s_f where s_f is the standard deviation of neuron f's pre-activation
@@ -41,10 +63,17 @@ def make_ffn_inputs(T, D, F, seed=0, zero_fraction=0.90, w_std=0.02):
     W1 = bf16_bits_from_f32(rng.standard_normal((F, D), dtype=np.float32) * np.float32(w_std))
     W2 = bf16_bits_from_f32(rng.standard_normal((D, F), dtype=np.float32) * np.float32(w_std))
     dY = bf16_bits_from_f32(rng.standard_normal((T, D), dtype=np.float32))
-    z = Z_FOR_ZERO_FRACTION[zero_fraction] if zero_fraction in Z_FOR_ZERO_FRACTION else float(zero_fraction)
-    sq = np.sort((_bits_to_f64(W1) ** 2).reshape(F, D // 4, 4), axis=-1)[..., 2:]
-    b1 = (-z * np.sqrt(sq.sum(axis=(1, 2)))).astype(np.float32)
+    b1 = bias_for_zero_fraction(neuron_std(W1), zero_fraction)
     return dict(X=X, W1=W1, W2=W2, b1=b1, dY=dY)
+
+
+def make_ffn_sweep(T, D, F, zero_fractions, seed=0, w_std=0.02):
+    """The inputs of make_ffn_inputs for several zero fractions: X, W1, W2, dY are the same arrays (same seed), only the
+    bias shift differs.  Yields (zero_fraction, inputs)."""
+    base = make_ffn_inputs(T, D, F, seed, zero_fractions[0], w_std)
+    std = neuron_std(base["W1"])
+    for zf in zero_fractions:
+        yield zf, dict(base, b1=bias_for_zero_fraction(std, zf))
 
 
 def make_moe_segments(n_tokens=16384, n_experts=8, top_k=2, seed=0, align=64):
