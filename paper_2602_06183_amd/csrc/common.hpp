@@ -3,6 +3,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// Tile rows per band of the workgroup -> tile map of the 256 x 256 tile kernels: the 32 workgroups that an XCD runs at a time
+// cover GROUP tile rows x 32 / GROUP tile columns, and its L2 fetches the operand panels of exactly those rows and columns.
+#ifndef SFFN_TILE_GROUP
+#define SFFN_TILE_GROUP 4
+#endif
+
 namespace sffn {
 
 __device__ __forceinline__ float bf2f(uint32_t h) { return __uint_as_float(h << 16); }

@@ -97,7 +97,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     }
     int tm, tn;
     {
-        constexpr int GROUP = 4;
+        constexpr int GROUP = SFFN_TILE_GROUP;
         const int width = GROUP * tiles_n, group = L / width, first = group * GROUP;
         const int gsz = (tiles_m - first) < GROUP ? (tiles_m - first) : GROUP;
         tm = first + (L % width) % gsz;

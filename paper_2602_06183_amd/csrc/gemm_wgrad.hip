@@ -57,7 +57,7 @@ __global__ void __launch_bounds__(512) wgrad_vnm_kernel(const uint16_t* __restri
     }
     int tm, tn;
     {
-        constexpr int GROUP = 4;
+        constexpr int GROUP = SFFN_TILE_GROUP;
         const int width = GROUP * tiles_n, group = L / width, first = group * GROUP;
         const int gsz = (tiles_m - first) < GROUP ? (tiles_m - first) : GROUP;
         tm = first + (L % width) % gsz;
