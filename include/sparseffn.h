@@ -206,6 +206,19 @@ int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, 
                     const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
                     uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
 
+/* ffn_sparse_step for callers that cannot allocate device memory or hand over a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as ffn_sparse_step, but the
+ * workspace is a device array built into the library (SFFN_NOALLOC_WORKSPACE_MAX bytes, held by every GPU the library has
+ * run on until the process ends); the call allocates and frees nothing.  Shapes whose sffn_workspace_bytes() exceed that
+ * size are refused with SFFN_EWORKSPACE before anything is enqueued (e.g. T = 1024, D = 512, F = 2048 fits; the benchmark
+ * layers do not: they take ffn_sparse_step).  The intermediates stay inside the library.  All calls on one GPU share the
+ * one array: calls that overlap in time on the same GPU (two streams, two threads) race; calls on one stream are ordered
+ * and need no clearing in between, whatever their shapes. */
+#define SFFN_NOALLOC_WORKSPACE_MAX (32u << 20)
+int ffn_sparse_step_noalloc(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, const uint16_t* W2,
+                            const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
+                            uint16_t* dW2, void* stream);
+
 /* Mixture-of-experts form of the step (Section 1 states the method carries over to MoE FFNs; every expert is
  * one Alg. 1 + Alg. 2 FFN): n_experts (1..64) experts with their own weights, each applied to one consecutive
  * segment of the T token rows.  seg_offsets is a HOST array of n_experts + 1 ascending multiples of 64 with

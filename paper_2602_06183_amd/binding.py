@@ -63,6 +63,7 @@ def load():
     lib.dsqrelu_vnm.argtypes = [p, p, p, p, i64, i64, i32, i32, p, p]
     lib.vnm_wgrad.argtypes = [p, p, p, p, i64, i64, i64, i32, i32, i32, p, p, sz, p]
     lib.ffn_sparse_step.argtypes = [ctypes.POINTER(_Cfg)] + [p] * 9 + [p, sz, p]
+    lib.ffn_sparse_step_noalloc.argtypes = [ctypes.POINTER(_Cfg)] + [p] * 9 + [p]
     lib.sffn_grouped_workspace_bytes.restype = sz
     lib.sffn_grouped_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg), i32]
     lib.sffn_grouped_workspace_layout.argtypes = [ctypes.POINTER(_Cfg), i32, ctypes.POINTER(_Layout)]
@@ -386,6 +387,27 @@ def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD, keep_dense=True, M=8):
     step = FfnStep(T, D, F, mode, X.device, keep_dense, M)
     out = step(X, W1, W2, b1, dY)
     return out, step
+
+
+NOALLOC_WORKSPACE_MAX = 32 << 20
+
+
+def ffn_sparse_step_noalloc(X, W1, W2, b1, dY, out, mode=MODE_HARD, M=8):
+    """ffn_sparse_step_noalloc: the library's built-in workspace, nothing allocated by the call.  out = (Y3, dX, dW1, dW2),
+    allocated by the caller beforehand (this wrapper allocates nothing either)."""
+    if X is None or X.dim() != 2 or W1 is None or W1.dim() != 2:
+        raise SffnError("ffn_sparse_step_noalloc: X and W1 must be 2-D tensors")
+    T, D = X.shape
+    F = W1.shape[0]
+    Y3, dX, dW1, dW2 = out
+    for name, t, shape, kinds, opt in (("X", X, (T, D), _BF16, False), ("W1", W1, (F, D), _BF16, False), ("W2", W2, (D, F), _BF16, False),
+                                       ("b1", b1, (F,), _F32, True), ("dY", dY, (T, D), _BF16, False), ("Y3", Y3, (T, D), _BF16, False),
+                                       ("dX", dX, (T, D), _BF16, False), ("dW1", dW1, (F, D), _BF16, False), ("dW2", dW2, (D, F), _BF16, False)):
+        _want("ffn_sparse_step_noalloc: " + name, t, shape, kinds, optional=opt)
+    c = _cfg(T, D, F, mode, M=M)
+    _check(load().ffn_sparse_step_noalloc(ctypes.byref(c), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY), _ptr(Y3), _ptr(dX),
+                                          _ptr(dW1), _ptr(dW2), _stream()))
+    return out
 
 
 def venom_route_launch(X, means, M, want_scores=False):
