@@ -293,7 +293,7 @@ def main():
                          % ("ffn_router_step_ref" if args.router else "ffn_sparse_step_ref", Ts, T, Fs, F, " of expert 0" if hw.moe else "", dt)}
 
     # ================= the other configurations, stand-alone kernels, micro-benchmarks =============================
-    configs, kernels, gemm24, venom, router = None, None, None, None, None
+    configs, kernels, gemm24, venom, router, fp8_bench = None, None, None, None, None, None
     if not args.headline_only and not args.router and M == 8:
         esteps, ewarm = max(3, min(args.steps, 10)), max(1, min(args.warmup, 2))
         configs = {}
@@ -360,7 +360,23 @@ def main():
         t_p = ms_of(lambda: sffn.prune24_compress(gw, False, mode))
         gemm24 = {"shape_mnk": [4096, 16384, 4096], "dense_ms": round(t_d, 4), "spmm24_ms": round(t_s, 4), "prune24_ms": round(t_p, 4),
                   "speedup_vs_dense": round(t_d / t_s, 3), "speedup_with_pruning": round(t_d / (t_s + t_p), 3)}
-        del gx, gw, gout, gv, gm
+        # ---- the same contraction with fp8 (E4M3) operands (Section 3.4, closing paragraph): quantisation fused into the pruning pass,
+        #      v_smfmac_f32_32x32x64_fp8_fp8; peak for this dtype is the dense fp8 matrix rate, 5.0 PFLOP/s ------------------------
+        sx8, sw8 = float(gx.float().abs().max()) / 448.0, float(gw.float().abs().max()) / 448.0
+        gxq = sffn.quantize_fp8(gx, sx8)
+        gc8, gm8 = sffn.prune24_compress_fp8(gw, sw8, False, mode)
+        t_s8 = ms_of(lambda: sffn.spmm24_fp8(gxq, sx8, gc8, gm8, sw8))
+        t_p8 = ms_of(lambda: sffn.prune24_compress_fp8(gw, sw8, False, mode))
+        t_q8 = ms_of(lambda: sffn.quantize_fp8(gx, sx8))
+        alg8 = 4096.0 * 16384 * 4096                      # non-zero multiply-adds x 2 (half of k survives)
+        fp8_bench = {"shape_mnk": [4096, 16384, 4096], "dense_bf16_ms": round(t_d, 4), "spmm24_bf16_ms": round(t_s, 4), "spmm24_fp8_ms": round(t_s8, 4),
+                     "prune24_compress_fp8_ms": round(t_p8, 4), "quantize_fp8_X_ms": round(t_q8, 4),
+                     "prune24_compress_fp8 GB/s": round((2 + 0.5 + 0.125) * 16384 * 4096 / (t_p8 * 1e-3) / 1e9, 1),
+                     "speedup_vs_dense_bf16": round(t_d / t_s8, 3), "speedup_vs_dense_bf16_with_pruning_and_quantisation": round(t_d / (t_s8 + t_p8 + t_q8), 3),
+                     "speedup_vs_sparse_bf16": round(t_s / t_s8, 3),
+                     "roofline": {"bound": "mfma", "dtype": "fp8 (e4m3)", "peak": 5000.0, "unit": "TFLOP/s", "achieved": round(alg8 / (t_s8 * 1e-3) / 1e12, 2),
+                                  "frac": round(alg8 / (t_s8 * 1e-3) / 1e12 / 5000.0, 4), "issued": round(2 * alg8 / (t_s8 * 1e-3) / 1e12, 2)}}
+        del gx, gw, gout, gv, gm, gxq, gc8, gm8
 
         # ---- at the 1B shape: the activation GEMM alone for every block width of Table 5 against the dense GEMM of the same
         #      shape (Section 5.2.3's Venom micro-benchmark; out[T, D] = y2v[T, F] @ W1[F, D], eq. (7)'s orientation), and the
@@ -419,6 +435,7 @@ def main():
         "standalone_kernels": kernels,
         "venom_gemm_microbench": venom,
         "gemm24_microbench": gemm24,
+        "fp8_microbench": fp8_bench,
         "router_conversion": router,
         "roofline": roofline, "cpu_baseline": cpu,
         "paper_context": "paper reports 1.4-1.5x for 2:4 GEMMs and 1.4-1.7x end-to-end on NVIDIA sparse tensor cores (Sections 1, 5.2.3); context, not a target",

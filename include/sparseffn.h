@@ -139,6 +139,34 @@ int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_co
               const uint16_t* G, int64_t T, int64_t F, int64_t N, int V, int M, int out_f_major,
               uint16_t* out, void* workspace, size_t ws_bytes, void* stream);
 
+/* fp8 operands (Section 3.4, closing paragraph: quantisation is orthogonal to the two sparsities and can be fused into the
+ * sparsification scans; Section 1: the 2:4 hardware covers bf16 and fp8).  Format: OCP E4M3, finite-only (largest finite
+ * 448), one uint8 code per value.  One float32 `scale` per tensor, GIVEN by the caller (delayed scaling): a real x becomes
+ * code = E4M3_RNE(clamp(float32(x) * (1.0f / scale), -448, 448)); real ~ decode(code) * scale.  `amax` (optional device
+ * float, zeroed by the caller) receives, by atomic max, the largest magnitude that was quantised: the next step's scale is
+ * amax / 448.  Selection looks at the bf16 magnitudes BEFORE quantisation, so metadata and column indices are bit-identical
+ * to the bf16 entry points; only the stored survivors change (in SOFT mode the float32 a -/+ t goes straight to fp8).
+ *   quantize_fp8            the dense operand of eqs. (1), (3), (4), (7): n bf16 values -> n codes (n a multiple of 8)
+ *   prune24_compress_fp8    Section 2.2 + quantisation: arguments of prune24_compress; codes [R, K/2] u8, meta [R, K/8]
+ *   sqrelu_vnm_compress_fp8 eq. (2) + Section 2.3 + quantisation: arguments of sqrelu_vnm_compress; codes [T, 2F/M] u8
+ *   spmm24_fp8              eqs. (1), (4): out[t,n] = bf16( (sum_k dec(Xq[t,k]) dec(Ws[n,k])) * (scale_x*scale_w) + bias[n] ) on the
+ *                           fp8 structured-sparse matrix cores; Xq [T, K] codes, Ws packed ([N, K/2], [N, K/8]); K a multiple of 128
+ *   vnm_spmm_fp8            eqs. (3), (7): the V:N:M code matrix (a_codes [T, 2 Kfull/M]) times dense W codes, [N, Kfull]
+ *                           (w_kmajor = 0) or [Kfull, N] (1, contiguous rows); Kfull a multiple of 128, T below 65536;
+ *                           workspace: sffn_vnm_spmm_fp8_workspace_bytes()
+ * The weight gradients (eqs. (5), (8), contraction over tokens) have no fp8 form here. */
+int quantize_fp8(const uint16_t* src, int64_t n, float scale, uint8_t* codes, float* amax, void* stream);
+int prune24_compress_fp8(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float scale,
+                         uint8_t* codes, uint8_t* meta, float* amax, void* stream);
+int sqrelu_vnm_compress_fp8(const uint16_t* y1, int64_t T, int64_t F, int V, int M, float scale, uint8_t* codes,
+                            uint8_t* meta, uint8_t* colidx, float* amax, void* stream);
+int spmm24_fp8(const uint8_t* Xq, float scale_x, const uint8_t* w_codes, const uint8_t* w_meta, float scale_w,
+               const float* bias, int64_t T, int64_t N, int64_t K, uint16_t* out, void* stream);
+size_t sffn_vnm_spmm_fp8_workspace_bytes(int64_t T, int64_t N, int64_t Kfull);
+int vnm_spmm_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* a_colidx, float scale_a, const uint8_t* Wq,
+                 float scale_w, int w_kmajor, int64_t T, int64_t N, int64_t Kfull, int V, int M, uint16_t* out,
+                 void* workspace, size_t ws_bytes, void* stream);
+
 /* Section 3.3 / Alg. 3 ("Convert Activation to Venom") and the conversion steps 1-3 of Section 3.4: neuron-level
  * experts that produce the V:N:M activation directly.  Reading built here: E = M/4 experts; expert e owns the hidden
  * units f with (f mod M)/4 == e (the offline clustering is taken as already applied to W1's row order), so a block of

@@ -83,6 +83,14 @@ def load():
     lib.sffn_router_full_workspace_bytes.restype = sz
     lib.sffn_router_full_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg)]
     lib.ffn_router_full_step.argtypes = [ctypes.POINTER(_Cfg)] + [p] * 10 + [p, sz, p]
+    f32 = ctypes.c_float
+    lib.quantize_fp8.argtypes = [p, i64, f32, p, p, p]
+    lib.prune24_compress_fp8.argtypes = [p, i64, i64, i64, i32, i32, f32, p, p, p, p]
+    lib.sqrelu_vnm_compress_fp8.argtypes = [p, i64, i64, i32, i32, f32, p, p, p, p, p]
+    lib.spmm24_fp8.argtypes = [p, f32, p, p, f32, p, i64, i64, i64, p, p]
+    lib.sffn_vnm_spmm_fp8_workspace_bytes.restype = sz
+    lib.sffn_vnm_spmm_fp8_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.vnm_spmm_fp8.argtypes = [p, p, p, f32, p, f32, i32, i64, i64, i64, i32, i32, p, p, sz, p]
     lib.sffn_dense_sqrelu.argtypes = [p, p, i64, p]
     lib.sffn_dense_dsqrelu.argtypes = [p, p, p, i64, p]
     lib.sffn_profile_enable.argtypes = [i32]
@@ -387,6 +395,73 @@ def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD, keep_dense=True, M=8):
     step = FfnStep(T, D, F, mode, X.device, keep_dense, M)
     out = step(X, W1, W2, b1, dY)
     return out, step
+
+
+# ---- fp8 (E4M3) operands: Section 3.4's closing paragraph ---------------------------------------------------------------------
+def _amax_buf(want, dev):
+    return torch.zeros((1,), dtype=torch.float32, device=dev) if want else None
+
+
+def quantize_fp8(x, scale, want_amax=False):
+    """bf16 tensor -> E4M3 codes (uint8, same shape) with the caller's per-tensor scale; optionally also amax (device float [1])."""
+    if x is None or x.dtype not in _BF16 or x.numel() % 8:
+        raise SffnError("quantize_fp8: x must be a bf16 tensor with a multiple of 8 elements")
+    codes, amax = _u8(tuple(x.shape), x.device), _amax_buf(want_amax, x.device)
+    _check(load().quantize_fp8(_ptr(x), x.numel(), float(scale), _ptr(codes), _ptr(amax), _stream()))
+    return (codes, amax) if want_amax else codes
+
+
+def prune24_compress_fp8(src, scale, trans=False, mode=MODE_HARD, want_amax=False):
+    """As prune24_compress with the survivors stored as E4M3 codes: -> codes [R, K/2] u8, meta [R, K/8] (, amax)."""
+    if src is None or src.dim() != 2 or src.dtype not in _BF16:
+        raise SffnError("prune24_compress_fp8: src must be a 2-D bf16 tensor")
+    rows, cols = src.shape
+    R, K = (cols, rows) if trans else (rows, cols)
+    codes, meta, amax = _u8((R, K // 2), src.device), _u8((R, K // 8), src.device), _amax_buf(want_amax, src.device)
+    _check(load().prune24_compress_fp8(_ptr(src, True), R, K, src.stride(0), int(trans), mode, float(scale), _ptr(codes), _ptr(meta), _ptr(amax), _stream()))
+    return (codes, meta, amax) if want_amax else (codes, meta)
+
+
+def sqrelu_vnm_compress_fp8(y1, scale, V=64, M=8, want_amax=False):
+    if y1 is None or y1.dim() != 2 or y1.dtype not in _BF16:
+        raise SffnError("sqrelu_vnm_compress_fp8: y1 must be a 2-D bf16 tensor")
+    T, F = y1.shape
+    codes, meta = _u8((T, 2 * F // M), y1.device), _u8((T, F // (2 * M)), y1.device)
+    colidx, amax = _u8((T // V, F // M, 4), y1.device), _amax_buf(want_amax, y1.device)
+    _check(load().sqrelu_vnm_compress_fp8(_ptr(y1), T, F, V, M, float(scale), _ptr(codes), _ptr(meta), _ptr(colidx), _ptr(amax), _stream()))
+    return (codes, meta, colidx, amax) if want_amax else (codes, meta, colidx)
+
+
+def spmm24_fp8(Xq, scale_x, w_codes, w_meta, scale_w, bias=None):
+    if Xq is None or Xq.dim() != 2 or w_codes is None or w_codes.dim() != 2:
+        raise SffnError("spmm24_fp8: Xq and w_codes must be 2-D tensors")
+    T, K = Xq.shape
+    N = w_codes.shape[0]
+    _want("spmm24_fp8: Xq", Xq, (T, K), _U8)
+    _want("spmm24_fp8: w_codes", w_codes, (N, K // 2), _U8)
+    _want("spmm24_fp8: w_meta", w_meta, (N, K // 8), _U8)
+    _want("spmm24_fp8: bias", bias, (N,), _F32, optional=True)
+    out = _bf16((T, N), Xq.device)
+    _check(load().spmm24_fp8(_ptr(Xq), float(scale_x), _ptr(w_codes), _ptr(w_meta), float(scale_w), _ptr(bias), T, N, K, _ptr(out), _stream()))
+    return out
+
+
+def vnm_spmm_fp8(a_codes, a_meta, a_colidx, scale_a, Wq, scale_w, w_kmajor, V=64, M=8):
+    if a_codes is None or a_codes.dim() != 2 or Wq is None or Wq.dim() != 2:
+        raise SffnError("vnm_spmm_fp8: a_codes and Wq must be 2-D tensors")
+    T = a_codes.shape[0]
+    Kfull = a_codes.shape[1] * M // 2
+    N = Wq.shape[1] if w_kmajor else Wq.shape[0]
+    _want("vnm_spmm_fp8: a_codes", a_codes, (T, 2 * Kfull // M), _U8)
+    _want("vnm_spmm_fp8: a_meta", a_meta, (T, Kfull // (2 * M)), _U8)
+    _want("vnm_spmm_fp8: a_colidx", a_colidx, (T // V, Kfull // M, 4), _U8)
+    _want("vnm_spmm_fp8: Wq", Wq, (Kfull, N) if w_kmajor else (N, Kfull), _U8)
+    out = _bf16((T, N), a_codes.device)
+    nbytes = load().sffn_vnm_spmm_fp8_workspace_bytes(T, N, Kfull)
+    ws = _u8((max(nbytes, 16),), a_codes.device)
+    _check(load().vnm_spmm_fp8(_ptr(a_codes), _ptr(a_meta), _ptr(a_colidx), float(scale_a), _ptr(Wq), float(scale_w), int(w_kmajor), T, N, Kfull,
+                               V, M, _ptr(out), _ptr(ws), nbytes, _stream()))
+    return out
 
 
 NOALLOC_WORKSPACE_MAX = 32 << 20

@@ -242,6 +242,91 @@ int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_co
     return SFFN_OK;
 }
 
+// ---- Section 3.4, closing paragraph: fp8 (E4M3) operands, quantised inside the sparsification passes --------------------------
+static inline bool scale_ok(float s) { return s > 0.0f && s < 3.0e38f && (1.0f / s) < 3.0e38f; }
+inline bool mult128(int64_t v) { return v > 0 && (v % 128) == 0; }
+
+int quantize_fp8(const uint16_t* src, int64_t n, float scale, uint8_t* codes, float* amax, void* stream) {
+    REQUIRE(src && codes, SFFN_EINVAL, "quantize_fp8: null pointer");
+    REQUIRE(n > 0 && n % 8 == 0, SFFN_EINVAL, "quantize_fp8: n must be a positive multiple of 8");
+    REQUIRE(scale_ok(scale), SFFN_EINVAL, "quantize_fp8: scale must be a positive finite float");
+    REQUIRE(aligned16(src) && aligned16(codes) && ((uintptr_t)amax & 3u) == 0, SFFN_EINVAL, "quantize_fp8: pointers must be 16-byte aligned");
+    LAUNCH(launch_quantize_fp8(src, n, 1.0f / scale, codes, amax, (hipStream_t)stream), "quantize_fp8");
+    return SFFN_OK;
+}
+
+int prune24_compress_fp8(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float scale, uint8_t* codes, uint8_t* meta,
+                         float* amax, void* stream) {
+    REQUIRE(src && codes && meta, SFFN_EINVAL, "prune24_compress_fp8: null pointer");
+    REQUIRE(mult64(R) && mult64(K), SFFN_EINVAL, "prune24_compress_fp8: R and K must be positive multiples of 64");
+    REQUIRE(ld >= (trans ? R : K) && ld % 8 == 0, SFFN_EINVAL, "prune24_compress_fp8: ld too small or not a multiple of 8");
+    REQUIRE(mode == SFFN_MODE_HARD || mode == SFFN_MODE_SOFT, SFFN_EINVAL, "prune24_compress_fp8: unknown mode");
+    REQUIRE(trans == 0 || trans == 1, SFFN_EINVAL, "prune24_compress_fp8: trans must be 0 or 1");
+    REQUIRE(scale_ok(scale), SFFN_EINVAL, "prune24_compress_fp8: scale must be a positive finite float");
+    REQUIRE(aligned16(src) && aligned16(codes) && aligned16(meta) && ((uintptr_t)amax & 3u) == 0, SFFN_EINVAL, "prune24_compress_fp8: pointers must be 16-byte aligned");
+    REQUIRE(fits_int(R) && fits_int(K), SFFN_EUNSUPPORTED, "prune24_compress_fp8: dimension above 2^31");
+    LAUNCH(launch_prune24_fp8(src, R, K, ld, trans, mode, 1.0f / scale, codes, meta, amax, (hipStream_t)stream), "prune24_compress_fp8");
+    return SFFN_OK;
+}
+
+int sqrelu_vnm_compress_fp8(const uint16_t* y1, int64_t T, int64_t F, int V, int M, float scale, uint8_t* codes, uint8_t* meta, uint8_t* colidx,
+                            float* amax, void* stream) {
+    REQUIRE(y1 && codes && meta && colidx, SFFN_EINVAL, "sqrelu_vnm_compress_fp8: null pointer");
+    REQUIRE(mult64(T) && mult64(F), SFFN_EINVAL, "sqrelu_vnm_compress_fp8: T and F must be positive multiples of 64");
+    REQUIRE(vnm_ok(V, M), SFFN_EUNSUPPORTED, "sqrelu_vnm_compress_fp8: only V=64 with M in {8, 16, 32, 64} is built");
+    REQUIRE(F % (2 * M) == 0, SFFN_EINVAL, "sqrelu_vnm_compress_fp8: F must be a multiple of 2 M");
+    REQUIRE(scale_ok(scale), SFFN_EINVAL, "sqrelu_vnm_compress_fp8: scale must be a positive finite float");
+    REQUIRE(aligned16(y1) && aligned16(codes) && aligned16(meta) && aligned16(colidx) && ((uintptr_t)amax & 3u) == 0, SFFN_EINVAL,
+            "sqrelu_vnm_compress_fp8: pointers must be 16-byte aligned");
+    REQUIRE(fits_int(T) && fits_int(F) && T / 64 < 65536, SFFN_EUNSUPPORTED, "sqrelu_vnm_compress_fp8: T too large");
+    LAUNCH(launch_sqrelu_vnm_compress_fp8(y1, T, F, M, 1.0f / scale, codes, meta, colidx, amax, (hipStream_t)stream), "sqrelu_vnm_compress_fp8");
+    return SFFN_OK;
+}
+
+int spmm24_fp8(const uint8_t* Xq, float scale_x, const uint8_t* w_codes, const uint8_t* w_meta, float scale_w, const float* bias, int64_t T,
+               int64_t N, int64_t K, uint16_t* out, void* stream) {
+    REQUIRE(Xq && w_codes && w_meta && out, SFFN_EINVAL, "spmm24_fp8: null pointer");
+    REQUIRE(mult64(T) && mult64(N) && mult128(K), SFFN_EINVAL, "spmm24_fp8: T, N must be positive multiples of 64 and K of 128");
+    REQUIRE(scale_ok(scale_x) && scale_ok(scale_w), SFFN_EINVAL, "spmm24_fp8: scales must be positive finite floats");
+    REQUIRE(aligned16(Xq) && aligned16(w_codes) && aligned16(w_meta) && aligned16(out) && aligned16(bias), SFFN_EINVAL,
+            "spmm24_fp8: pointers must be 16-byte aligned");
+    REQUIRE(fits_int(T) && fits_int(N) && fits_int(K), SFFN_EUNSUPPORTED, "spmm24_fp8: dimension above 2^31");
+    LAUNCH(launch_spmm24_fp8(w_codes, w_meta, Xq, bias, scale_x * scale_w, N, T, K, 1, out, N, (hipStream_t)stream), "spmm24_fp8");
+    return SFFN_OK;
+}
+
+size_t sffn_vnm_spmm_fp8_workspace_bytes(int64_t T, int64_t N, int64_t Kfull) {
+    if (!mult64(T) || !mult64(N) || !mult128(Kfull)) return 0;
+    return up256((size_t)T * Kfull / 2) + up256((size_t)T * Kfull / 8) + up256((size_t)N * Kfull);
+}
+
+int vnm_spmm_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* a_colidx, float scale_a, const uint8_t* Wq, float scale_w,
+                 int w_kmajor, int64_t T, int64_t N, int64_t Kfull, int V, int M, uint16_t* out, void* workspace, size_t ws_bytes, void* stream) {
+    REQUIRE(a_codes && a_meta && a_colidx && Wq && out, SFFN_EINVAL, "vnm_spmm_fp8: null pointer");
+    REQUIRE(mult64(T) && mult64(N) && mult128(Kfull), SFFN_EINVAL, "vnm_spmm_fp8: T, N must be positive multiples of 64 and Kfull of 128");
+    REQUIRE(vnm_ok(V, M), SFFN_EUNSUPPORTED, "vnm_spmm_fp8: only V=64 with M in {8, 16, 32, 64} is built");
+    REQUIRE(Kfull % (2 * M) == 0, SFFN_EINVAL, "vnm_spmm_fp8: Kfull must be a multiple of 2 M");
+    REQUIRE(w_kmajor == 0 || w_kmajor == 1, SFFN_EINVAL, "vnm_spmm_fp8: w_kmajor must be 0 or 1");
+    REQUIRE(scale_ok(scale_a) && scale_ok(scale_w), SFFN_EINVAL, "vnm_spmm_fp8: scales must be positive finite floats");
+    REQUIRE(aligned16(a_codes) && aligned16(a_meta) && aligned16(a_colidx) && aligned16(Wq) && aligned16(out) && aligned16(workspace), SFFN_EINVAL,
+            "vnm_spmm_fp8: pointers must be 16-byte aligned");
+    REQUIRE(fits_int(T) && fits_int(N) && fits_int(Kfull) && T < 65536, SFFN_EUNSUPPORTED, "vnm_spmm_fp8: T must be below 65536");
+    REQUIRE(workspace && ws_bytes >= sffn_vnm_spmm_fp8_workspace_bytes(T, N, Kfull), SFFN_EWORKSPACE, "vnm_spmm_fp8: workspace missing or too small");
+    hipStream_t s = (hipStream_t)stream;
+    uint8_t* ws = (uint8_t*)workspace;
+    uint8_t* c24 = ws;
+    uint8_t* m24 = ws + up256((size_t)T * Kfull / 2);
+    uint8_t* wt = m24 + up256((size_t)T * Kfull / 8);
+    LAUNCH(launch_vnm_to_24_fp8(a_codes, a_meta, a_colidx, T, Kfull, M, c24, m24, s), "vnm_spmm_fp8/to24");
+    const uint8_t* W = Wq;
+    if (w_kmajor) {
+        LAUNCH(launch_transpose_u8(Wq, Kfull, N, N, wt, s), "vnm_spmm_fp8/transpose");
+        W = wt;
+    }
+    LAUNCH(launch_spmm24_fp8(c24, m24, W, nullptr, scale_a * scale_w, T, N, Kfull, 0, out, N, s), "vnm_spmm_fp8/gemm");
+    return SFFN_OK;
+}
+
 // ---- Section 3.3 / Alg. 3: neuron-level experts that emit the V:N:M format ----------------------------------------
 int64_t sffn_venom_rows(int64_t T, int M) {
     if (T < 0 || !vnm_ok(64, M)) return 0;

@@ -1,0 +1,294 @@
+// fp8 operands (paper Section 3.4, closing paragraph: quantisation fused into the sparsification scans; Section 1: the 2:4
+// hardware covers bf16 and fp8).  Format: OCP E4M3, finite-only (largest finite 448), which is what gfx950's matrix cores
+// and v_cvt_pk_fp8_f32 implement.  One float32 scale per tensor, given by the caller: code = E4M3_RNE(clamp(x * inv, +-448)),
+// inv = 1 / scale computed once on the host in float32.  Selection always looks at the bf16 magnitudes first, so positions,
+// metadata and column indices are those of the bf16 kernels; only the stored survivors become 1-byte codes.
+//   quantize_fp8_kernel            dense operand of eqs. (1), (3), (4), (7): plain scan
+//   prune24_rows_fp8 / cols_fp8    Section 2.2 (HARD / SOFT) + quantisation: codes [R, K/2], metadata [R, K/8]
+//   sqrelu_vnm_compress_fp8        eq. (2) + Section 2.3 + quantisation: codes [T, 2F/M], metadata, column indices
+//   vnm_to_24_fp8                  the V:2:M code matrix as a plain 2:4 code matrix over all columns (operand of eqs. (3), (7))
+//   transpose_u8                   [R, C] bytes -> [C, R]
+// Every kernel can record the largest magnitude it quantised (float32, atomic max on the bit pattern) for the caller's next scale.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace sffn {
+
+namespace {
+
+// two real values -> two E4M3 codes in the low 16 bits (first value in the low byte)
+__device__ __forceinline__ uint32_t enc2(float a, float b, float inv) {
+    const float ma = __builtin_fminf(__builtin_fmaxf(a * inv, -448.0f), 448.0f);
+    const float mb = __builtin_fminf(__builtin_fmaxf(b * inv, -448.0f), 448.0f);
+    return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(ma, mb, 0, false) & 0xFFFFu;
+}
+
+__device__ __forceinline__ void note_amax(float* amax, float m) {      // m >= 0; one atomic per wavefront
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) m = __builtin_fmaxf(m, __shfl_xor(m, o, 64));
+    if (amax && (threadIdx.x & 63) == 0) atomicMax(reinterpret_cast<unsigned int*>(amax), __float_as_uint(m));
+}
+
+// 2:4 selection as select24 (common.hpp) but returning the survivors as float32 reals: bit copies widened (HARD) or
+// a -/+ t evaluated in float32 (SOFT), not rounded to bf16.
+template <bool SOFT>
+__device__ __forceinline__ void select24_f32(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3, uint32_t& nib, float& f0, float& f1) {
+    const uint32_t m0 = a0 & 0x7FFFu, m1 = a1 & 0x7FFFu, m2 = a2 & 0x7FFFu, m3 = a3 & 0x7FFFu;
+    const int c01 = m0 >= m1, c02 = m0 >= m2, c03 = m0 >= m3, c12 = m1 >= m2, c13 = m1 >= m3, c23 = m2 >= m3;
+    const int r0 = 3 - c01 - c02 - c03, r1 = c01 + 2 - c12 - c13, r2 = c02 + c12 + 1 - c23, r3 = c03 + c13 + c23;
+    const bool k0 = r0 < 2, k1 = r1 < 2, k2 = r2 < 2, k3 = r3 < 2;
+    const uint32_t p0 = k0 ? 0u : (k1 ? 1u : 2u), p1 = k3 ? 3u : (k2 ? 2u : 1u);
+    const uint32_t v0 = k0 ? a0 : (k1 ? a1 : a2), v1 = k3 ? a3 : (k2 ? a2 : a1);
+    nib = p0 | (p1 << 2);
+    f0 = bf2f(v0); f1 = bf2f(v1);
+    if (SOFT) {
+        const float t = bf2f((r0 == 2) ? m0 : (r1 == 2) ? m1 : (r2 == 2) ? m2 : m3);
+        f0 = (v0 & 0x8000u) ? f0 + t : f0 - t;
+        f1 = (v1 & 0x8000u) ? f1 + t : f1 - t;
+    }
+}
+
+}  // namespace
+
+__global__ void __launch_bounds__(256) quantize_fp8_kernel(const uint4* __restrict__ src, int64_t n8, float inv, uint2* __restrict__ codes,
+                                                          float* __restrict__ amax) {
+    float m = 0.0f;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (int64_t)gridDim.x * 256) {
+        const uint4 w = src[i];
+        const float f[8] = {bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16),
+                            bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16)};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) m = __builtin_fmaxf(m, __builtin_fabsf(f[e]));
+        codes[i] = make_uint2(enc2(f[0], f[1], inv) | (enc2(f[2], f[3], inv) << 16), enc2(f[4], f[5], inv) | (enc2(f[6], f[7], inv) << 16));
+    }
+    note_amax(amax, m);
+}
+
+// rows K-contiguous: one thread per 8 consecutive elements (two groups) -> 4 codes + 1 metadata byte
+template <bool SOFT>
+__global__ void __launch_bounds__(256) prune24_rows_fp8_kernel(const uint16_t* __restrict__ src, int64_t nchunks, int cpr, int64_t ld, float inv,
+                                                              uint8_t* __restrict__ codes, uint8_t* __restrict__ meta, float* __restrict__ amax) {
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    float m = 0.0f;
+    if (c < nchunks) {
+        const int64_t r = c / cpr;
+        const uint4 w = *reinterpret_cast<const uint4*>(src + r * ld + (c - r * cpr) * 8);
+        uint32_t n0, n1;
+        float a, b, d, e;
+        select24_f32<SOFT>(w.x & 0xFFFFu, w.x >> 16, w.y & 0xFFFFu, w.y >> 16, n0, a, b);
+        select24_f32<SOFT>(w.z & 0xFFFFu, w.z >> 16, w.w & 0xFFFFu, w.w >> 16, n1, d, e);
+        m = __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(a), __builtin_fabsf(b)), __builtin_fmaxf(__builtin_fabsf(d), __builtin_fabsf(e)));
+        *reinterpret_cast<uint32_t*>(codes + c * 4) = enc2(a, b, inv) | (enc2(d, e, inv) << 16);
+        meta[c] = (uint8_t)(n0 | (n1 << 4));
+    }
+    note_amax(amax, m);
+}
+
+// groups run along the strided axis: S[r, k] = src[k * ld + r]; a workgroup takes 64 logical rows x 128 k through LDS
+template <bool SOFT>
+__global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* __restrict__ src, int64_t R, int K, int64_t ld, float inv,
+                                                              uint8_t* __restrict__ codes, uint8_t* __restrict__ meta, float* __restrict__ amax) {
+    constexpr int TK = 128, TR = 64, PITCH = TR + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t tile[TK * PITCH];
+    const int64_t r0 = (int64_t)blockIdx.x * TR;
+    const int k0 = blockIdx.y * TK;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int kk = tid / 8 + 32 * i, seg = tid % 8;
+        uint4 w = make_uint4(0, 0, 0, 0);
+        if (k0 + kk < K) w = *reinterpret_cast<const uint4*>(src + (int64_t)(k0 + kk) * ld + r0 + seg * 8);
+        *reinterpret_cast<uint4*>(&tile[kk * PITCH + seg * 8]) = w;
+    }
+    __syncthreads();
+    const int rr = tid % 64, q = tid / 64;
+    float m = 0.0f;
+    if (k0 + 32 * q < K) {
+        uint32_t oc[4], mbytes = 0;
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            const uint16_t* p = &tile[(32 * q + 4 * g) * PITCH + rr];
+            uint32_t nib;
+            float a, b;
+            select24_f32<SOFT>(p[0], p[PITCH], p[2 * PITCH], p[3 * PITCH], nib, a, b);
+            m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(a), __builtin_fabsf(b)));
+            const uint32_t c2 = enc2(a, b, inv);
+            if (g & 1) oc[g >> 1] |= c2 << 16; else oc[g >> 1] = c2;
+            mbytes |= nib << (4 * g);
+        }
+        const int64_t r = r0 + rr;
+        *reinterpret_cast<uint4*>(codes + r * (K / 2) + (k0 + 32 * q) / 2) = make_uint4(oc[0], oc[1], oc[2], oc[3]);
+        *reinterpret_cast<uint32_t*>(meta + r * (K / 8) + (k0 + 32 * q) / 8) = mbytes;
+    }
+    note_amax(amax, m);
+}
+
+// eq. (2) + V:N:M compression with fp8 values: the structure of sqrelu_vnm_compress_m_kernel (vnm_general.hip): one workgroup =
+// one 64-token block x 256 columns, wavefront w owns 64 columns; scores, column choice and the per-row 2:4 choice on the bf16 y2.
+template <int M>
+__global__ void __launch_bounds__(256) sqrelu_vnm_compress_fp8_kernel(const uint16_t* __restrict__ y1, int64_t F, float inv, uint8_t* __restrict__ codes,
+                                                                     uint8_t* __restrict__ meta, uint8_t* __restrict__ colidx, float* __restrict__ amax) {
+    constexpr int NB = 64 / M, PITCH = 64 * 2 + 16;
+    __shared__ __attribute__((aligned(16))) unsigned char tiles[4][64 * PITCH];
+    __shared__ uint8_t nibs[64][256 / M];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t tb = blockIdx.y;
+    const int64_t c0 = (int64_t)blockIdx.x * 256 + wave * 64;
+    const bool active = c0 < F;
+    unsigned char* tl = tiles[wave];
+    float mx = 0.0f;
+    if (active) {
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int row = it * 8 + (lane >> 3), seg = lane & 7;
+            const uint4 w = *reinterpret_cast<const uint4*>(y1 + (tb * 64 + row) * F + c0 + seg * 8);
+            const uint32_t in[4] = {w.x, w.y, w.z, w.w};
+            uint32_t o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float a = bf2f(in[e] & 0xFFFFu), b = bf2f(in[e] >> 16);
+                const float ra = a > 0.0f ? a : 0.0f, rb = b > 0.0f ? b : 0.0f;
+                o[e] = f2bf2(ra * ra, rb * rb);
+            }
+            *reinterpret_cast<uint4*>(tl + row * PITCH + seg * 16) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    }
+    __syncthreads();
+    if (active) {
+        float sc = 0.0f;                                  // strict ascending-row fp32 sum of y2
+#pragma unroll 8
+        for (int r = 0; r < 64; ++r) sc = sc + bf2f(*reinterpret_cast<const uint16_t*>(tl + r * PITCH + lane * 2));
+        const int c = lane % M, base = lane - c;
+        int rank = 0;
+        for (int k = 0; k < M; ++k) {
+            const float o = __shfl(sc, base + k, 64);
+            rank += (k < c) ? (o >= sc) : ((k > c) ? (o > sc) : 0);
+        }
+        const unsigned long long kept = __ballot(rank < 4);
+        unsigned long long bits = (M == 64) ? kept : ((kept >> base) & ((1ull << (M & 63)) - 1ull));
+        uint32_t cw = 0;
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+            cw |= (uint32_t)__builtin_ctzll(bits) << (8 * n);
+            bits &= bits - 1ull;
+        }
+        if (c == 0) *reinterpret_cast<uint32_t*>(colidx + (tb * (F / M) + (c0 + base) / M) * 4) = cw;
+#pragma unroll
+        for (int sweep = 0; sweep < NB; ++sweep) {
+            const int pair = sweep * 64 + lane, row = pair / NB, b = pair % NB;
+            const uint32_t cb = (uint32_t)__shfl((int)cw, b * M, 64);
+            const unsigned char* rp = tl + row * PITCH + b * M * 2;
+            const uint32_t y0 = *reinterpret_cast<const uint16_t*>(rp + (cb & 0xFFu) * 2);
+            const uint32_t y1v = *reinterpret_cast<const uint16_t*>(rp + ((cb >> 8) & 0xFFu) * 2);
+            const uint32_t y2v = *reinterpret_cast<const uint16_t*>(rp + ((cb >> 16) & 0xFFu) * 2);
+            const uint32_t y3v = *reinterpret_cast<const uint16_t*>(rp + (cb >> 24) * 2);
+            uint32_t nib;
+            float a, bb;
+            select24_f32<false>(y0, y1v, y2v, y3v, nib, a, bb);
+            mx = __builtin_fmaxf(mx, __builtin_fmaxf(a, bb));
+            *reinterpret_cast<uint16_t*>(codes + (tb * 64 + row) * (2 * F / M) + (c0 / M + b) * 2) = (uint16_t)enc2(a, bb, inv);
+            nibs[row][wave * NB + b] = (uint8_t)nib;
+        }
+    }
+    __syncthreads();
+    constexpr int BYTES = 128 / M;
+    for (int e = threadIdx.x; e < 64 * BYTES; e += 256) {
+        const int row = e / BYTES, j = e % BYTES;
+        if ((int64_t)blockIdx.x * 256 + 2 * j * M < F)
+            meta[(tb * 64 + row) * (F / (2 * M)) + (int64_t)blockIdx.x * BYTES + j] = (uint8_t)(nibs[row][2 * j] | (nibs[row][2 * j + 1] << 4));
+    }
+    note_amax(amax, mx);
+}
+
+// The V:2:M code matrix as a plain 2:4 code matrix over all F columns: codes24 [T, F/2], meta24 [T, F/8] (row-major); a group holds
+// both survivors, one (next to an empty slot, code 0 = +0) or none.  One thread per (token, block).
+__global__ void __launch_bounds__(256) vnm_to_24_fp8_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ meta,
+                                                           const uint8_t* __restrict__ colidx, int64_t F, int M, int nblk,
+                                                           uint8_t* __restrict__ codes24, uint8_t* __restrict__ meta24) {
+    const int blk = blockIdx.x * 256 + threadIdx.x;
+    if (blk >= nblk) return;
+    const int64_t t = blockIdx.y;
+    const uint32_t cw = *reinterpret_cast<const uint32_t*>(colidx + ((t >> 6) * nblk + blk) * 4);
+    const uint32_t nib = (meta[t * (nblk / 2) + (blk >> 1)] >> (4 * (blk & 1))) & 0xFu;
+    const uint32_t v = *reinterpret_cast<const uint16_t*>(codes + t * (2 * (int64_t)nblk) + (int64_t)blk * 2);
+    const uint32_t o0 = (cw >> (8 * (nib & 3u))) & 0xFFu, o1 = (cw >> (8 * (nib >> 2))) & 0xFFu;    // o0 < o1
+    const uint32_t v0 = v & 0xFFu, v1 = v >> 8;
+    uint16_t* vo = reinterpret_cast<uint16_t*>(codes24 + t * (F / 2) + (int64_t)blk * (M / 2));
+    uint8_t* mo = meta24 + t * (F / 8) + (int64_t)blk * (M / 8);
+    uint32_t prev = 0;
+    for (int g = 0; g < M / 4; ++g) {
+        const bool in0 = (o0 >> 2) == (uint32_t)g, in1 = (o1 >> 2) == (uint32_t)g;
+        const uint32_t p = o0 & 3u, q = o1 & 3u;
+        uint32_t a = 0, n = 0x4u;                                   // empty group: +0 at positions 0, 1
+        if (in0 && in1) { a = v; n = p | (q << 2); }
+        else if (in0)   { a = (p < 3) ? v0 : (v0 << 8); n = (p < 3) ? (p | (3u << 2)) : (3u << 2); }
+        else if (in1)   { a = (q > 0) ? (v1 << 8) : v1; n = (q > 0) ? (q << 2) : 0x4u; }
+        vo[g] = (uint16_t)a;
+        if (g & 1) mo[g >> 1] = (uint8_t)(prev | (n << 4)); else prev = n;
+    }
+}
+
+__global__ void __launch_bounds__(256) transpose_u8_kernel(const uint8_t* __restrict__ in, int64_t R, int64_t C, int64_t ld, uint8_t* __restrict__ out) {
+    __shared__ uint8_t tile[64][64 + 4];
+    const int tid = threadIdx.x;
+    const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = tid / 16 + 16 * i, seg = tid % 16;
+        *reinterpret_cast<uint32_t*>(&tile[r][seg * 4]) = *reinterpret_cast<const uint32_t*>(in + (r0 + r) * ld + c0 + seg * 4);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = tid / 16 + 16 * i, seg = tid % 16;
+        const uint32_t w = tile[seg * 4][c] | (tile[seg * 4 + 1][c] << 8) | (tile[seg * 4 + 2][c] << 16) | ((uint32_t)tile[seg * 4 + 3][c] << 24);
+        *reinterpret_cast<uint32_t*>(out + (c0 + c) * R + r0 + seg * 4) = w;
+    }
+}
+
+hipError_t launch_quantize_fp8(const uint16_t* src, int64_t n, float inv, uint8_t* codes, float* amax, hipStream_t s) {
+    const int64_t n8 = n / 8, blocks = (n8 + 255) / 256;
+    hipLaunchKernelGGL(quantize_fp8_kernel, dim3((unsigned)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, s, (const uint4*)src, n8, inv, (uint2*)codes, amax);
+    return hipGetLastError();
+}
+
+hipError_t launch_prune24_fp8(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
+                              float* amax, hipStream_t s) {
+    if (!trans) {
+        const int64_t nchunks = R * (K / 8);
+        const unsigned grid = (unsigned)((nchunks + 255) / 256);
+        if (mode == 0) hipLaunchKernelGGL((prune24_rows_fp8_kernel<false>), dim3(grid), dim3(256), 0, s, src, nchunks, (int)(K / 8), ld, inv, codes, meta, amax);
+        else           hipLaunchKernelGGL((prune24_rows_fp8_kernel<true>), dim3(grid), dim3(256), 0, s, src, nchunks, (int)(K / 8), ld, inv, codes, meta, amax);
+    } else {
+        dim3 grid((unsigned)(R / 64), (unsigned)((K + 127) / 128));
+        if (mode == 0) hipLaunchKernelGGL((prune24_cols_fp8_kernel<false>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax);
+        else           hipLaunchKernelGGL((prune24_cols_fp8_kernel<true>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_sqrelu_vnm_compress_fp8(const uint16_t* y1, int64_t T, int64_t F, int M, float inv, uint8_t* codes, uint8_t* meta, uint8_t* colidx,
+                                          float* amax, hipStream_t s) {
+    dim3 grid((unsigned)((F + 255) / 256), (unsigned)(T / 64));
+    if (M == 8)       hipLaunchKernelGGL((sqrelu_vnm_compress_fp8_kernel<8>), grid, dim3(256), 0, s, y1, F, inv, codes, meta, colidx, amax);
+    else if (M == 16) hipLaunchKernelGGL((sqrelu_vnm_compress_fp8_kernel<16>), grid, dim3(256), 0, s, y1, F, inv, codes, meta, colidx, amax);
+    else if (M == 32) hipLaunchKernelGGL((sqrelu_vnm_compress_fp8_kernel<32>), grid, dim3(256), 0, s, y1, F, inv, codes, meta, colidx, amax);
+    else if (M == 64) hipLaunchKernelGGL((sqrelu_vnm_compress_fp8_kernel<64>), grid, dim3(256), 0, s, y1, F, inv, codes, meta, colidx, amax);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_vnm_to_24_fp8(const uint8_t* codes, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F, int M, uint8_t* codes24,
+                                uint8_t* meta24, hipStream_t s) {
+    const int nblk = (int)(F / M);
+    dim3 grid((unsigned)((nblk + 255) / 256), (unsigned)T);
+    hipLaunchKernelGGL(vnm_to_24_fp8_kernel, grid, dim3(256), 0, s, codes, meta, colidx, F, M, nblk, codes24, meta24);
+    return hipGetLastError();
+}
+
+hipError_t launch_transpose_u8(const uint8_t* in, int64_t R, int64_t C, int64_t ld, uint8_t* out, hipStream_t s) {
+    hipLaunchKernelGGL(transpose_u8_kernel, dim3((unsigned)(C / 64), (unsigned)(R / 64)), dim3(256), 0, s, in, R, C, ld, out);
+    return hipGetLastError();
+}
+
+}  // namespace sffn

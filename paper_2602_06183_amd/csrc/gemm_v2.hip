@@ -15,16 +15,21 @@ namespace sffn {
 
 namespace {
 
-template <bool SPARSE>
+// FP8 (structured-sparse kernel on row-major operands only): both operands are 1-byte E4M3 codes.  In BYTES the tiles are those of
+// the bf16 kernel (a stage is 128 k instead of 64: 64 survivor bytes per A row, 128 bytes per B row, and the fragment a lane of
+// v_smfmac_f32_32x32x64_fp8_fp8 wants is the same 16 / 2 x 16 bytes), so the kernel runs with K counted in byte pairs and only
+// the metadata differs: 16 survivors per lane and step need a whole 32-bit index word, 16 bytes per row and stage.
+template <bool SPARSE, bool FP8 = false>
 struct Cfg {
     static constexpr int BM = 256, BN = 256;
     static constexpr int BK = SPARSE ? 64 : 32;
     static constexpr int NSTAGE = SPARSE ? 3 : 4;
     static constexpr int A_ROW = 64;                        // bytes per A row per stage (32 survivors or 32 dense k)
     static constexpr int B_ROW = SPARSE ? 128 : 64;
-    static constexpr int A_BYTES = BM * A_ROW, B_BYTES = BN * B_ROW, META_BYTES = SPARSE ? BM * 8 : 0;
+    static constexpr int META_ROW = FP8 ? 16 : 8;
+    static constexpr int A_BYTES = BM * A_ROW, B_BYTES = BN * B_ROW, META_BYTES = SPARSE ? BM * META_ROW : 0;
     static constexpr int STAGE = A_BYTES + B_BYTES + META_BYTES;
-    static constexpr int LOADS = (A_BYTES + B_BYTES) / 1024 / 8 + (SPARSE ? 1 : 0);   // per wave per stage
+    static constexpr int LOADS = (A_BYTES + B_BYTES) / 1024 / 8 + (SPARSE ? (FP8 ? 2 : 1) : 0);   // per wave per stage
 };
 
 }  // namespace
@@ -36,14 +41,15 @@ __device__ __forceinline__ uint32_t sqrelu16(uint32_t y) {
     return f2bf(r * r);
 }
 __device__ __forceinline__ uint32_t sqrelu_hi(uint32_t y) { return sqrelu16(y) << 16; }
-template <bool SPARSE, bool OUT_I_CONTIG, int EPI, bool BLOCKED>
+template <bool SPARSE, bool OUT_I_CONTIG, int EPI, bool BLOCKED, bool FP8 = false>
 __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restrict__ a_vals, const uint8_t* __restrict__ a_meta,
                                                         const uint16_t* __restrict__ B, const float* __restrict__ bias,
                                                         int Ra, int Rb, int K, uint16_t* __restrict__ out, int64_t ldo,
-                                                        int tiles_m, int tiles_n, VnmEpilogue ep, GemmGroup grp) {
+                                                        int tiles_m, int tiles_n, VnmEpilogue ep, GemmGroup grp, float alpha = 1.0f) {
     static_assert(EPI == 0 || (SPARSE && OUT_I_CONTIG && BLOCKED), "the V:N:M epilogues belong to the 2:4-weight GEMMs of the fused step");
+    static_assert(!FP8 || (SPARSE && !BLOCKED && EPI == 0), "fp8 operands: structured-sparse kernel on row-major operands");
     constexpr bool blocked = BLOCKED;       // operands in the blocked layout of common.hpp (fused step) or row-major (stand-alone entry points)
-    using C = Cfg<SPARSE>;
+    using C = Cfg<SPARSE, FP8>;
     constexpr int BM = C::BM, BN = C::BN, WM = 128, WN = 64, FM = 4, FN = 2;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[C::NSTAGE * C::STAGE];
 
@@ -146,13 +152,15 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         // metadata: one 4-byte-per-lane load brings 32 rows x 64 k; blocked: one unit of common.hpp, lane-linear;
         // row-major: lane -> (row lane / 2, 4-byte half lane % 2), landing as [row][8 bytes]
         m_lane = blocked ? lane * 4 : (uint32_t)((lane >> 1) * (Kld / 8) + (lane & 1) * 4);
+        // fp8: a row has Kld / 4 metadata bytes, 16 per stage; one load brings 16 rows (lane -> row lane / 4, word lane % 4), two per wave
+        if (FP8) m_lane = (uint32_t)((lane >> 2) * (Kld / 4) + (lane & 3) * 4);
         if (SPARSE) {
             int gr = i0 + wave * 32; gr = gr < Ra ? gr : Ra - 32;
-            m_base = uniform64(blocked ? a_meta + ((int64_t)(gr >> 5) * (Kld / 64) << 8) : a_meta + (int64_t)gr * (Kld / 8));
+            m_base = uniform64(blocked ? a_meta + ((int64_t)(gr >> 5) * (Kld / 64) << 8) : a_meta + (int64_t)gr * (FP8 ? Kld / 4 : Kld / 8));
         }
         a_kstep = blocked ? 1024 : 64;
         b_kstep = blocked ? 1024 * (C::BK / 32) : C::BK * 2;
-        m_kstep = blocked ? 256 : 8;
+        m_kstep = blocked ? 256 : C::META_ROW;
     }
     // the DMA loads of one stage, issued in two halves (h = 0, 1) so that they can sit between matrix instructions
     auto issue_half = [&](int kt, int stage, int h) {
@@ -170,7 +178,11 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
             const uint32_t bo = b_lane + (uint32_t)kt * b_kstep, bo1 = b_lane1 + (uint32_t)kt * b_kstep;
 #pragma unroll
             for (int n = B_LD / 2; n < B_LD; ++n) dma16(b_base[n], (lineB && (n & 1)) ? bo1 : bo, sb + (wave * B_LD + n) * 1024);
-            if (SPARSE) dma4(m_base, m_lane + (uint32_t)kt * m_kstep, sm + wave * 256);
+            if (SPARSE && !FP8) dma4(m_base, m_lane + (uint32_t)kt * m_kstep, sm + wave * 256);
+            if (FP8) {
+                dma4(m_base, m_lane + (uint32_t)kt * m_kstep, sm + wave * 512);
+                dma4(m_base, m_lane + (uint32_t)(16 * (Kld / 4)) + (uint32_t)kt * m_kstep, sm + wave * 512 + 256);
+            }
         }
     };
     auto issue = [&](int kt, int stage) { issue_half(kt, stage, 0); issue_half(kt, stage, 1); };
@@ -182,7 +194,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         const int row = wm * WM + a * 32 + l32;
         a_off[a] = row * 64 + ((lh ^ ((row >> 2) & 3)) << 4);
         // blocked: the lane's word of unit row / 32 holds both 32-k steps (picked by ABID); row-major: [row][8 bytes]
-        m_off[a] = C::A_BYTES + C::B_BYTES + (blocked ? (row >> 5) * 256 + lane * 4 : row * 8 + 2 * lh);
+        m_off[a] = C::A_BYTES + C::B_BYTES + (blocked ? (row >> 5) * 256 + lane * 4 : FP8 ? row * 16 + 4 * lh : row * 8 + 2 * lh);
     }
 #pragma unroll
     for (int b = 0; b < FN; ++b) {
@@ -211,7 +223,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     auto read_a = [&](FragSet& f, const FragSet& prev, const unsigned char* st, int ks, int a) {
         f.a[a].u = *reinterpret_cast<const uint4*>(st + (a_off[a] ^ (32 * ks)));
         if (SPARSE) {
-            if (!blocked) f.idx[a] = *reinterpret_cast<const uint16_t*>(st + m_off[a] + 4 * ks);
+            if (FP8) f.idx[a] = *reinterpret_cast<const uint32_t*>(st + m_off[a] + 8 * ks);
+            else if (!blocked) f.idx[a] = *reinterpret_cast<const uint16_t*>(st + m_off[a] + 4 * ks);
             else if (ks == 0) f.idx[a] = *reinterpret_cast<const uint32_t*>(st + m_off[a]);
             else f.idx[a] = prev.idx[a];
         }
@@ -238,7 +251,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     auto mma_row = [&](const FragSet& f, int a, bool second) {
 #pragma unroll
         for (int b = 0; b < FN; ++b) {
-            if (!SPARSE)                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a].v, f.b8[b].v, acc[a][b], 0, 0, 0);
+            if (FP8)                    acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x64_fp8_fp8(f.a[a].q, f.b16[b].q, acc[a][b], f.idx[a], 0, 0);
+            else if (!SPARSE)           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a].v, f.b8[b].v, acc[a][b], 0, 0, 0);
             else if (blocked && second) acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[a].v, f.b16[b].v, acc[a][b], f.idx[a], 0, 1);
             else                        acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[a].v, f.b16[b].v, acc[a][b], f.idx[a], 0, 0);
         }
@@ -336,8 +350,14 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                     for (int g = 0; g < 4; ++g) {
                         const int a = 2 * h + a2;
                         const int il = a2 * 32 + 8 * g + 4 * lh;              // i inside the 64-wide half
-                        const float v0 = acc[a][b][4 * g] + bb[a2][g].x, v1 = acc[a][b][4 * g + 1] + bb[a2][g].y;
-                        const float v2 = acc[a][b][4 * g + 2] + bb[a2][g].z, v3 = acc[a][b][4 * g + 3] + bb[a2][g].w;
+                        float v0, v1, v2, v3;
+                        if (FP8) {      // codes were multiplied: the product of the two tensor scales comes first, one rounding, then the bias
+                            v0 = acc[a][b][4 * g] * alpha + bb[a2][g].x;     v1 = acc[a][b][4 * g + 1] * alpha + bb[a2][g].y;
+                            v2 = acc[a][b][4 * g + 2] * alpha + bb[a2][g].z; v3 = acc[a][b][4 * g + 3] * alpha + bb[a2][g].w;
+                        } else {
+                            v0 = acc[a][b][4 * g] + bb[a2][g].x;     v1 = acc[a][b][4 * g + 1] + bb[a2][g].y;
+                            v2 = acc[a][b][4 * g + 2] + bb[a2][g].z; v3 = acc[a][b][4 * g + 3] + bb[a2][g].w;
+                        }
                         *reinterpret_cast<uint2*>(scratch + (b * 32 + l32) * EP + il * 2) =
                             tok_ok[b] ? make_uint2(f2bf2(v0, v1), f2bf2(v2, v3)) : make_uint2(0u, 0u);
                     }
@@ -528,7 +548,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = 8 * (r >> 2) + 4 * lh + (r & 3);
-                    *reinterpret_cast<uint16_t*>(scratch + row * EP + (b * 32 + l32) * 2) = (uint16_t)f2bf(acc[a][b][r]);
+                    *reinterpret_cast<uint16_t*>(scratch + row * EP + (b * 32 + l32) * 2) = (uint16_t)f2bf(FP8 ? acc[a][b][r] * alpha : acc[a][b][r]);
                 }
             __syncthreads();
             constexpr int CH = WN / 8;
@@ -585,6 +605,25 @@ hipError_t launch_gemm_nt(int sparse_a, const uint16_t* a_vals, const uint8_t* a
                              const GemmGroup* grp) {
     if (sparse_a) return grp ? hipErrorInvalidValue : launch_v2<true>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s, nullptr);
     return launch_v2<false>(a_vals, a_meta, B, bias, Ra, Rb, K, out_i_contig, out, ldo, 0, s, grp);
+}
+
+hipError_t launch_spmm24_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* Bq, const float* bias, float alpha, int64_t Ra, int64_t Rb,
+                             int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
+    if (K % 128 != 0) return hipErrorInvalidValue;
+    const int tiles_m = (int)((Ra + 255) / 256), tiles_n = (int)((Rb + 255) / 256);
+    const VnmEpilogue none;
+    const GemmGroup g;
+    dim3 grid((unsigned)(tiles_m * tiles_n));
+    // the kernel addresses its operands in 2-byte units: K / 2 of them per B row, K / 4 per A row
+    const uint16_t* a = reinterpret_cast<const uint16_t*>(a_codes);
+    const uint16_t* b = reinterpret_cast<const uint16_t*>(Bq);
+    if (out_i_contig)
+        hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 0, false, true>), grid, dim3(512), 0, s, a, a_meta, b, bias, (int)Ra, (int)Rb, (int)(K / 2), out, ldo,
+                           tiles_m, tiles_n, none, g, alpha);
+    else
+        hipLaunchKernelGGL((gemm_nt_v2_kernel<true, false, 0, false, true>), grid, dim3(512), 0, s, a, a_meta, b, bias, (int)Ra, (int)Rb, (int)(K / 2), out, ldo,
+                           tiles_m, tiles_n, none, g, alpha);
+    return hipGetLastError();
 }
 
 hipError_t launch_spmm_blocked(const uint16_t* a_vals, const uint8_t* a_meta, const uint16_t* B, const float* bias, int64_t Ra, int64_t Rb,

@@ -132,6 +132,21 @@ hipError_t launch_fill_tail_rows(const TailFill& f, const int32_t* first_dev, in
                                  hipStream_t s);
 hipError_t launch_venom_colidx(const GemmGroup& g, int64_t cap, int64_t groups, uint8_t* colidx, hipStream_t s);
 
+// fp8 operands (fp8.hip; Section 3.4's closing paragraph): E4M3 codes, inv = 1 / scale; amax (optional, device float) receives the largest
+// magnitude quantised through an atomic max.
+hipError_t launch_quantize_fp8(const uint16_t* src, int64_t n, float inv, uint8_t* codes, float* amax, hipStream_t s);
+hipError_t launch_prune24_fp8(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
+                              float* amax, hipStream_t s);
+hipError_t launch_sqrelu_vnm_compress_fp8(const uint16_t* y1, int64_t T, int64_t F, int M, float inv, uint8_t* codes, uint8_t* meta, uint8_t* colidx,
+                                          float* amax, hipStream_t s);
+hipError_t launch_vnm_to_24_fp8(const uint8_t* codes, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F, int M, uint8_t* codes24,
+                                uint8_t* meta24, hipStream_t s);
+hipError_t launch_transpose_u8(const uint8_t* in, int64_t R, int64_t C, int64_t ld, uint8_t* out, hipStream_t s);
+// C[i, j] = alpha * sum_k dec(A[i, k]) * dec(B[j, k]) (+ bias[i] when out_i_contig) on v_smfmac_f32_32x32x64_fp8_fp8: A packed 2:4 codes
+// [Ra, K/2] + metadata [Ra, K/8], B codes [Rb, K], both row-major; K a multiple of 128; out bf16 as launch_gemm_nt.
+hipError_t launch_spmm24_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* Bq, const float* bias, float alpha, int64_t Ra, int64_t Rb,
+                             int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
+
 hipError_t launch_wgrad_vnm(const uint16_t* atc, const uint8_t* kmask, const uint16_t* G, int64_t F, int64_t N, int64_t T,
                             int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 

@@ -7,6 +7,10 @@
 //                               B: lane l -> column l%32; elements 0-7 = k 8*(l/32)..+7, elements 8-15 = k 16+8*(l/32)..+7;
 //                               D: lane l, register r -> row 8*(r/4) + 4*(l/32) + r%4, column l%32.
 //   v_mfma_f32_32x32x16_bf16    A, B: lane l -> row / column l%32, k 8*(l/32)..+7;  D as above.
+//   v_smfmac_f32_32x32x64_fp8_fp8  A: lane l -> row l%32, the 16 survivors (one byte each) of k in 32*(l/32)..+31, index VGPR bits
+//                                  [2e+1:2e] = position of survivor e inside its group of 4 (all 32 bits are used, no ABID);
+//                               B: lane l -> column l%32; bytes 0-15 = k 16*(l/32)..+15, bytes 16-31 = k 32+16*(l/32)..+15;  D as above.
+//                               (byte for byte the bf16 instruction's operand layout with twice the k per byte)
 // The 2-bit positions are exactly the packed format's metadata nibbles, so metadata goes from HBM to the index
 // VGPR without re-encoding.
 #pragma once
@@ -18,8 +22,10 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-union Frag8 { uint4 u; bf16x8 v; };
-union Frag16 { uint4 u[2]; bf16x16 v; };
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+union Frag8 { uint4 u; bf16x8 v; i32x4 q; };            // q: the same 16 bytes as 16 fp8 codes
+union Frag16 { uint4 u[2]; bf16x16 v; i32x8 q; };
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void glb_void;

@@ -1,0 +1,162 @@
+"""GPU parity of the fp8 entry points (paper Section 3.4, closing paragraph) against oracle/fp8.py on identical seeded inputs:
+codes, metadata and column indices bit-exact; contractions within the GEMM tolerance of the oracle's exact sum over the same codes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import fp8
+import paper_2602_06183_amd as sffn
+from tests.util import to_dev, to_bits, assert_gemm_close, gemm_errors
+from workload import bf16_bits_from_f32, make_ffn_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def rnd_bits(rng, shape, scale=1.0):
+    return bf16_bits_from_f32(rng.standard_normal(shape, dtype=np.float32) * np.float32(scale))
+
+
+def u8(t):
+    return t.detach().cpu().numpy()
+
+
+def test_quantize_fp8_every_bf16_pattern_and_scales():
+    """All 65536 bf16 bit patterns that are finite, at several scales (powers of two and not), saturation included."""
+    allbits = np.arange(65536, dtype=np.uint16)
+    finite = (allbits & 0x7F80) != 0x7F80
+    x = np.ascontiguousarray(allbits[finite][: (finite.sum() // 8) * 8])
+    for scale in (1.0, 0.02 * 4 / 448, 7.0, 2.0 ** -12, 3.1e-3, 1000.0):
+        got, amax = sffn.quantize_fp8(to_dev(x), scale, want_amax=True)
+        assert np.array_equal(u8(got), fp8.quantize_fp8(x, scale)), scale
+        assert float(amax.cpu()[0]) == float(fp8.amax(x))
+
+
+@pytest.mark.parametrize("mode", [sffn.MODE_HARD, sffn.MODE_SOFT])
+@pytest.mark.parametrize("R,K,trans", [(64, 64, 0), (192, 320, 0), (448, 2048, 0), (64, 64, 1), (192, 320, 1), (1024, 256, 1)])
+def test_prune24_compress_fp8(R, K, trans, mode):
+    from tests.test_gpu_kernels import adversarial_rows
+    rng = np.random.default_rng(R + 3 * K + trans)
+    S = rnd_bits(rng, (R, K), 0.02)
+    adv = adversarial_rows(K)
+    S[: adv.shape[0]] = adv
+    S[20, :8] = bf16_bits_from_f32(np.array([1.0703125, 2.0, 0.0068359375, 0.001, 30.0, -30.0, 29.0, 1.0], dtype=np.float32))
+    scale = 0.05 / 448
+    stored = np.ascontiguousarray(S.T) if trans else S
+    codes, meta, amax = sffn.prune24_compress_fp8(to_dev(stored), scale, bool(trans), mode, want_amax=True)
+    rc, rm = fp8.prune24_compress_fp8(S, scale, mode)
+    assert np.array_equal(u8(meta), rm)
+    assert np.array_equal(u8(codes), rc)
+    _, rm16 = oracle.prune24_compress(S, mode)
+    assert np.array_equal(u8(meta), rm16)                          # same selection as the bf16 path
+    if mode == sffn.MODE_HARD:
+        rv, _ = oracle.prune24_compress(S, mode)
+        finite = rv[(rv & 0x7F80) != 0x7F80]
+        assert float(amax.cpu()[0]) == float(fp8.amax(finite))
+
+
+@pytest.mark.parametrize("M", [8, 16, 32, 64])
+@pytest.mark.parametrize("T,F", [(64, 256), (192, 1152)])
+def test_sqrelu_vnm_compress_fp8(T, F, M):
+    rng = np.random.default_rng(T + F + M)
+    y1 = bf16_bits_from_f32(rng.standard_normal((T, F), dtype=np.float32) - np.float32(0.8))
+    y1[:64, 0:M] = 0xBF80
+    y1[:64, M:2 * M] = 0x3F80
+    y1[:64, 2 * M:2 * M + 4] = 0x4580                              # 4096^2 = 2^24: saturates the fp8 range at this scale
+    scale = 12.0 / 448
+    codes, meta, colidx = sffn.sqrelu_vnm_compress_fp8(to_dev(y1), scale, 64, M)
+    rc, rm, ri = fp8.sqrelu_vnm_compress_fp8(y1, scale, 64, M)
+    assert np.array_equal(u8(colidx), ri) and np.array_equal(u8(meta), rm)
+    assert np.array_equal(u8(codes), rc)
+    _, m16, c16 = oracle.sqrelu_vnm_compress(y1, 64, M)
+    assert np.array_equal(u8(meta), m16) and np.array_equal(u8(colidx), c16)
+
+
+@pytest.mark.parametrize("T,N,K", [(64, 64, 128), (192, 320, 384), (512, 1024, 256), (384, 256, 2048)])
+def test_spmm24_fp8(T, N, K):
+    rng = np.random.default_rng(T + 3 * N + 7 * K)
+    X = rnd_bits(rng, (T, K))
+    W = rnd_bits(rng, (N, K), 0.02)
+    bias = rng.standard_normal(N).astype(np.float32)
+    sx, sw = 4.0 / 448, 0.08 / 448
+    xq = fp8.quantize_fp8(X, sx)
+    wc, wm = fp8.prune24_compress_fp8(W, sw, oracle.sparse24.SOFT)
+    dxq, dwc, dwm = torch.from_numpy(xq).cuda(), torch.from_numpy(wc).cuda(), torch.from_numpy(wm).cuda()
+    assert_gemm_close(to_bits(sffn.spmm24_fp8(dxq, sx, dwc, dwm, sw, to_dev(bias))), fp8.spmm24_fp8(xq, sx, wc, wm, sw, bias), "fp8 fwd+bias")
+    assert_gemm_close(to_bits(sffn.spmm24_fp8(dxq, sx, dwc, dwm, sw, None)), fp8.spmm24_fp8(xq, sx, wc, wm, sw, None), "fp8 fwd")
+    # how far the quantised contraction is from the bf16 one on the same inputs (reported; 3 mantissa bits per factor)
+    v16, m16 = oracle.prune24_compress(W, oracle.sparse24.SOFT)
+    fro, _ = gemm_errors(fp8.spmm24_fp8(xq, sx, wc, wm, sw, None), oracle.spmm24(X, v16, m16, None))
+    print("fp8 vs bf16 contraction, relative Frobenius distance: %.4f" % fro)
+    assert fro < 0.08
+
+
+def test_spmm24_fp8_exact_on_small_integers():
+    """Small integers are exact in E4M3 (scale 1) and their products and sums exact in fp32: the fp8 matrix cores must then
+    reproduce the bf16 oracle bit for bit, which pins the operand / metadata layout of the fp8 instruction."""
+    rng = np.random.default_rng(7)
+    T, N, K = 128, 192, 256
+    X = bf16_bits_from_f32(rng.integers(-3, 4, (T, K)).astype(np.float32))
+    W = bf16_bits_from_f32(rng.integers(-3, 4, (N, K)).astype(np.float32))
+    wc, wm = sffn.prune24_compress_fp8(to_dev(W), 1.0)
+    got = to_bits(sffn.spmm24_fp8(sffn.quantize_fp8(to_dev(X), 1.0), 1.0, wc, wm, 1.0))
+    v16, m16 = oracle.prune24_compress(W)
+    assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.spmm24(X, v16, m16, None)))
+    y1 = bf16_bits_from_f32(rng.integers(-2, 4, (T, K)).astype(np.float32))
+    for M in (8, 32):
+        ac, am, ai = sffn.sqrelu_vnm_compress_fp8(to_dev(y1), 1.0, 64, M)
+        av, _, _ = oracle.sqrelu_vnm_compress(y1, 64, M)
+        Wd = bf16_bits_from_f32(rng.integers(-3, 4, (N, K)).astype(np.float32))
+        for kmaj, w in ((0, Wd), (1, np.ascontiguousarray(Wd.T))):
+            got = to_bits(sffn.vnm_spmm_fp8(ac, am, ai, 1.0, sffn.quantize_fp8(to_dev(w), 1.0), 1.0, kmaj, 64, M))
+            assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.vnm_spmm(av, u8(am), u8(ai), w, kmaj, 64, M)))
+
+
+@pytest.mark.parametrize("M", [8, 16])
+@pytest.mark.parametrize("T,F,D", [(64, 128, 64), (192, 384, 320), (256, 2048, 192)])
+def test_vnm_spmm_fp8(T, F, D, M):
+    rng = np.random.default_rng(T + 3 * F + 7 * D + M)
+    y1 = bf16_bits_from_f32(rng.standard_normal((T, F), dtype=np.float32) - np.float32(0.8))
+    W2 = rnd_bits(rng, (D, F), 0.02)
+    W1 = rnd_bits(rng, (F, D), 0.02)
+    sa, sw = 12.0 / 448, 0.08 / 448
+    ac, am, ai = fp8.sqrelu_vnm_compress_fp8(y1, sa, 64, M)
+    dac, dam, dai = (torch.from_numpy(a).cuda() for a in (ac, am, ai))
+    for kmaj, w in ((0, W2), (1, W1)):
+        wq = fp8.quantize_fp8(w, sw)
+        got = sffn.vnm_spmm_fp8(dac, dam, dai, sa, torch.from_numpy(wq).cuda(), sw, kmaj, 64, M)
+        assert_gemm_close(to_bits(got), fp8.vnm_spmm_fp8(ac, am, ai, sa, wq, sw, kmaj, 64, M), "fp8 vnm_spmm kmajor=%d" % kmaj)
+
+
+def test_fp8_forward_chain_at_the_1b_shape():
+    """eq. (1) -> eq. (2) + V:N:M -> eq. (3) with fp8 operands at the 1B layer shape, scales from the tensors' own amax (as a
+    delayed-scaling recipe would carry them over), teacher-forced on sampled rows / token blocks."""
+    T, D, F = 8192, 2048, 8192
+    inp = make_ffn_inputs(T, D, F, seed=0)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    sx = float(fp8.amax(inp["X"])) / 448
+    sw1 = float(fp8.amax(inp["W1"])) / 448
+    sw2 = float(fp8.amax(inp["W2"])) / 448
+    xq = sffn.quantize_fp8(dev["X"], sx)
+    wc, wm = sffn.prune24_compress_fp8(dev["W1"], sw1)
+    y1 = sffn.spmm24_fp8(xq, sx, wc, wm, sw1, dev["b1"])
+    sy = 16.0 / 448
+    ac, am, ai, amax = sffn.sqrelu_vnm_compress_fp8(y1, sy, 64, 8, want_amax=True)
+    w2q = sffn.quantize_fp8(dev["W2"], sw2)
+    y3 = sffn.vnm_spmm_fp8(ac, am, ai, sy, w2q, sw2, 0)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    rows = np.sort(rng.choice(T, 32, replace=False))
+    rc, rm = fp8.prune24_compress_fp8(inp["W1"], sw1)
+    assert np.array_equal(u8(wc), rc) and np.array_equal(u8(wm), rm)
+    xq_ref = fp8.quantize_fp8(inp["X"][rows], sx)
+    assert np.array_equal(u8(xq)[rows], xq_ref)
+    y1b = to_bits(y1)
+    assert_gemm_close(y1b[rows], fp8.spmm24_fp8(xq_ref, sx, rc, rm, sw1, inp["b1"]), "fp8 y1 rows")
+    for tb in (0, 57, 127):
+        r = slice(64 * tb, 64 * tb + 64)
+        oc, om, oi = fp8.sqrelu_vnm_compress_fp8(y1b[r], sy)
+        assert np.array_equal(u8(ai)[tb:tb + 1], oi) and np.array_equal(u8(am)[r], om) and np.array_equal(u8(ac)[r], oc)
+        w2q_ref = fp8.quantize_fp8(inp["W2"], sw2)
+        assert_gemm_close(to_bits(y3)[r], fp8.vnm_spmm_fp8(oc, om, oi, sy, w2q_ref, sw2, 0), "fp8 y3 block")
+    assert 0 < float(amax.cpu()[0]) < 1e4
