@@ -245,6 +245,10 @@ def main():
     kos = dict(KERNEL_OF_STAGE)
     if "step/dX" in acc and "step/W1.T" not in acc and M == 8:      # eq. (7) ran on the gathered-row kernel (no transpose of W1 in the step)
         kos["step/dX"] = "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>"
+    if M != 8:      # wide blocks: eqs. (3), (7) gather rows, eqs. (5), (8) contract the dense transposed activation with the dense-operand tile kernel
+        if "step/to24(y2)" not in acc:
+            kos.update({"step/y3": "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>", "step/dX": "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>"})
+        kos.update({"step/dW2": DENSE_GEMM, "step/dW1": DENSE_GEMM})
     for name, ms in acc.items():
         by_kernel.setdefault(kos.get(name, name), []).append((name, ms))
     dom_kernel = max(by_kernel, key=lambda k: sum(ms for _, ms in by_kernel[k]))

@@ -55,7 +55,7 @@ typedef struct sffn_cfg {
     int64_t D;      /* d_model */
     int64_t F;      /* d_ffn */
     int32_t V;      /* V:N:M block height, 64 */
-    int32_t M;      /* V:N:M block width: 8 (fused kernels), or 16 / 32 / 64 (unfused path, see ffn_sparse_step) */
+    int32_t M;      /* V:N:M block width: 8, 16, 32 or 64 (Table 5) */
     int32_t mode;   /* SFFN_MODE_HARD or SFFN_MODE_SOFT for both weight sparsifiers */
     int32_t flags;  /* SFFN_FLAG_* */
 } sffn_cfg;
@@ -65,6 +65,10 @@ typedef struct sffn_cfg {
  * y2's kept slots (y1_kept).  With this flag the step also stores the dense y1 and dy2 (same kernels, same
  * arithmetic, two extra [T,F] writes), which is what lets a checker reproduce every stage bit for bit. */
 #define SFFN_FLAG_KEEP_DENSE 1
+/* Blocks of 16 / 32 / 64 columns only: run the unfused path (eqs. (2), (6) as separate kernels, the dense y1 and dy2 through
+ * HBM, 15 launches).  It is what the fused path is checked against bit for bit; shapes the gathered-row kernel does not cover
+ * (4 F / M not a multiple of 64 or above 7168) take it in any case. */
+#define SFFN_FLAG_UNFUSED 2
 
 /* Byte offsets, inside the workspace of ffn_sparse_step, of the tensors Alg. 2 line 1 saves
  * from the forward pass and of the other intermediates (all filled when the step returns). */
@@ -76,8 +80,9 @@ typedef struct sffn_ws_layout {
     size_t y2_vals, y2_meta, colidx;/* V:N:M y2: [T, F/4] bf16, [T, F/16] u8, [T/64, F/8, 4] u8 */
     size_t dy2;                     /* [T, F] bf16, eq. (4); present under the same condition as y1 */
     size_t dy1_vals;                /* [T, F/4] bf16, eq. (6) in y2's slots */
-    size_t y1_kept;                 /* T*F/4 bf16, y1 at y2's kept slots (what Alg. 2 line 1 needs of y1), stored as
-                                     * [T/64][F/64][64 tokens][8 column blocks][2] */
+    size_t y1_kept;                 /* T*2F/M bf16, y1 at y2's kept slots (what Alg. 2 line 1 needs of y1), stored as
+                                     * [T/64][F/64][64 tokens][64/M column blocks][2]; absent (0 bytes) on the unfused path */
+    size_t y1_kept_bytes;
     size_t total;                   /* bytes needed */
 } sffn_ws_layout;
 
@@ -227,9 +232,10 @@ int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint1
 /* Alg. 1 + Alg. 2, one call: X [T,D], W1 [F,D], W2 [D,F], b1 fp32 [F] or NULL, dY [T,D] ->
  * Y3 [T,D], dX [T,D], dW1 [F,D], dW2 [D,F]; intermediates land in `workspace` at the offsets of
  * sffn_workspace_layout().  Both weight matrices are re-pruned inside the call.
- * cfg->M = 16, 32 or 64 (Table 5): the same algorithm without the fused epilogues: eqs. (2), (6) run as separate
- * kernels, eqs. (3), (7) contract only the kept rows of W2.T / W1 (see vnm_spmm; same fallback rule); the dense y1 and
- * dy2 are then always stored, y1_kept is not produced, and the packed activation tensors have the sizes given above. */
+ * cfg->M = 16, 32 or 64 (Table 5): the same algorithm and the same fusion; eqs. (3), (7) contract only the kept rows of
+ * W2.T / W1 (see vnm_spmm), and the packed activation tensors have the sizes given above.  Shapes whose 4 F / M is not a
+ * multiple of 64 or exceeds 7168, and calls with SFFN_FLAG_UNFUSED, run eqs. (2), (6) as separate kernels instead: the dense
+ * y1 and dy2 are then always stored and y1_kept is not produced. */
 int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, const uint16_t* W2,
                     const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
                     uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
@@ -253,7 +259,8 @@ int ffn_sparse_step_noalloc(const sffn_cfg* cfg, const uint16_t* X, const uint16
  * seg_offsets[0] = 0 and seg_offsets[n_experts] = cfg->T (it is read during the call, not afterwards); a segment
  * may be empty, its expert then gets zero weight gradients.  Rows the caller pads a segment with must be zero in X
  * and dY.  X, dY, Y3, dX: [T, D]; W1, dW1: [n_experts, F, D]; W2, dW2: [n_experts, D, F]; b1: [n_experts, F] or NULL.
- * Every stage is a single launch over all experts.  The workspace has the layout of ffn_sparse_step with every
+ * Every stage is a single launch over all experts (cfg->M = 16, 32, 64: fused path only, SFFN_EUNSUPPORTED for shapes it does
+ * not cover).  The workspace has the layout of ffn_sparse_step with every
  * weight-shaped tensor holding n_experts matrices back to back (sffn_grouped_workspace_layout()).  The router,
  * the token permutation and the weighted combine of an MoE layer are outside this library. */
 size_t sffn_grouped_workspace_bytes(const sffn_cfg* cfg, int n_experts);

@@ -24,7 +24,7 @@ class _Cfg(ctypes.Structure):
 
 class _Layout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta", "y1", "y2_vals", "y2_meta",
-                                               "colidx", "dy2", "dy1_vals", "y1_kept", "total")]
+                                               "colidx", "dy2", "dy1_vals", "y1_kept", "y1_kept_bytes", "total")]
 
 
 class _RouterLayout(ctypes.Structure):
@@ -163,6 +163,7 @@ def profile_read():
 
 
 FLAG_KEEP_DENSE = 1
+FLAG_UNFUSED = 2
 
 
 def dense_sqrelu(y1, out):
@@ -184,13 +185,17 @@ def _cfg(T, D, F, mode=MODE_HARD, V=64, M=8, flags=0):
     return _Cfg(T, D, F, V, M, mode, flags)
 
 
-def workspace_bytes(T, D, F, mode=MODE_HARD, M=8, keep_dense=False):
-    c = _cfg(T, D, F, mode, M=M, flags=FLAG_KEEP_DENSE if keep_dense else 0)
+def _flags(keep_dense, unfused=False):
+    return (FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_UNFUSED if unfused else 0)
+
+
+def workspace_bytes(T, D, F, mode=MODE_HARD, M=8, keep_dense=False, unfused=False):
+    c = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused))
     return load().sffn_workspace_bytes(ctypes.byref(c))
 
 
-def workspace_layout(T, D, F, mode=MODE_HARD, M=8, keep_dense=False):
-    c, lay = _cfg(T, D, F, mode, M=M, flags=FLAG_KEEP_DENSE if keep_dense else 0), _Layout()
+def workspace_layout(T, D, F, mode=MODE_HARD, M=8, keep_dense=False, unfused=False):
+    c, lay = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused)), _Layout()
     _check(load().sffn_workspace_layout(ctypes.byref(c), ctypes.byref(lay)))
     return {n: getattr(lay, n) for n, _ in _Layout._fields_}
 
@@ -294,13 +299,13 @@ def vnm_wgrad(a_vals, a_meta, a_colidx, G, out_f_major, V=64, M=8):
 class FfnStep:
     """Pre-allocated outputs and workspace for repeated ffn_sparse_step calls on one shape."""
 
-    def __init__(self, T, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8):
+    def __init__(self, T, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8, unfused=False):
         """keep_dense: also store the dense y1 and dy2 (SFFN_FLAG_KEEP_DENSE); otherwise only y1 at y2's kept
-        slots is saved for the backward pass.  M: V:N:M block width, 8 (fused kernels) or 16 / 32 / 64 (unfused
-        path that always stores y1 and dy2 and produces no y1_kept)."""
+        slots is saved for the backward pass.  M: V:N:M block width, 8, 16, 32 or 64.  unfused (M >= 16): the path
+        with separate eq. (2) / eq. (6) kernels that always stores y1 and dy2 and produces no y1_kept."""
         self.T, self.D, self.F, self.mode, self.keep_dense, self.M = T, D, F, mode, keep_dense, M
-        self.cfg = _cfg(T, D, F, mode, M=M, flags=FLAG_KEEP_DENSE if keep_dense else 0)
-        self.layout = workspace_layout(T, D, F, mode, M, keep_dense)
+        self.cfg = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused))
+        self.layout = workspace_layout(T, D, F, mode, M, keep_dense, unfused)
         self.ws = _u8((self.layout["total"],), device)
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
         self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
@@ -332,10 +337,10 @@ class FfnStep:
                    y2_vals=view(L["y2_vals"], (T, 2 * F // M), torch.bfloat16),
                    y2_meta=view(L["y2_meta"], (T, F // (2 * M)), torch.uint8), colidx=view(L["colidx"], (T // 64, F // M, 4), torch.uint8),
                    dy1_vals=view(L["dy1_vals"], (T, 2 * F // M), torch.bfloat16))
-        if self.keep_dense or M != 8:       # the dense y1 / dy2 have room in the workspace only when they are stored
+        if L["y2_vals"] > L["y1"]:          # the dense y1 / dy2 have room in the workspace only when they are stored
             out["y1"], out["dy2"] = view(L["y1"], (T, F), torch.bfloat16), view(L["dy2"], (T, F), torch.bfloat16)
-        if M == 8:
-            out["y1_kept"] = view(L["y1_kept"], (T, F // 4), torch.bfloat16)
+        if L["y1_kept_bytes"]:
+            out["y1_kept"] = view(L["y1_kept"], (T, 2 * F // M), torch.bfloat16)
         return out
 
 
@@ -343,11 +348,11 @@ class FfnStepGrouped:
     """Pre-allocated outputs and workspace for ffn_sparse_step_grouped: n_experts FFNs, expert e on token rows
     seg[e]..seg[e+1] (host integers, multiples of 64; T = seg[-1])."""
 
-    def __init__(self, seg, D, F, mode=MODE_HARD, device="cuda", keep_dense=False):
+    def __init__(self, seg, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8):
         self.seg = [int(v) for v in seg]
-        self.E, self.T, self.D, self.F, self.mode, self.keep_dense = len(self.seg) - 1, self.seg[-1], D, F, mode, keep_dense
+        self.E, self.T, self.D, self.F, self.mode, self.keep_dense, self.M = len(self.seg) - 1, self.seg[-1], D, F, mode, keep_dense, M
         self.seg_c = (ctypes.c_int64 * len(self.seg))(*self.seg)
-        self.cfg = _cfg(self.T, D, F, mode, flags=FLAG_KEEP_DENSE if keep_dense else 0)
+        self.cfg = _cfg(self.T, D, F, mode, M=M, flags=FLAG_KEEP_DENSE if keep_dense else 0)
         lay = _Layout()
         _check(load().sffn_grouped_workspace_layout(ctypes.byref(self.cfg), self.E, ctypes.byref(lay)))
         self.layout = {n: getattr(lay, n) for n, _ in _Layout._fields_}
@@ -369,7 +374,7 @@ class FfnStepGrouped:
 
     def saved(self):
         """As FfnStep.saved(); weight-shaped tensors carry a leading expert axis."""
-        T, D, F, E, L = self.T, self.D, self.F, self.E, self.layout
+        T, D, F, E, L, M = self.T, self.D, self.F, self.E, self.layout, self.M
 
         def view(off, shape, dtype):
             n = 1
@@ -380,19 +385,19 @@ class FfnStepGrouped:
 
         out = dict(w1_vals=view(L["w1_vals"], (E, F, D // 2), torch.bfloat16), w1_meta=view(L["w1_meta"], (E, F, D // 8), torch.uint8),
                    w2t_vals=view(L["w2t_vals"], (E, F, D // 2), torch.bfloat16), w2t_meta=view(L["w2t_meta"], (E, F, D // 8), torch.uint8),
-                   y2_vals=view(L["y2_vals"], (T, F // 4), torch.bfloat16),
-                   y2_meta=view(L["y2_meta"], (T, F // 16), torch.uint8), colidx=view(L["colidx"], (T // 64, F // 8, 4), torch.uint8),
-                   dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16),
-                   y1_kept=view(L["y1_kept"], (T, F // 4), torch.bfloat16))
+                   y2_vals=view(L["y2_vals"], (T, 2 * F // M), torch.bfloat16),
+                   y2_meta=view(L["y2_meta"], (T, F // (2 * M)), torch.uint8), colidx=view(L["colidx"], (T // 64, F // M, 4), torch.uint8),
+                   dy1_vals=view(L["dy1_vals"], (T, 2 * F // M), torch.bfloat16),
+                   y1_kept=view(L["y1_kept"], (T, 2 * F // M), torch.bfloat16))
         if self.keep_dense:
             out["y1"], out["dy2"] = view(L["y1"], (T, F), torch.bfloat16), view(L["dy2"], (T, F), torch.bfloat16)
         return out
 
 
-def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD, keep_dense=True, M=8):
+def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD, keep_dense=True, M=8, unfused=False):
     T, D = X.shape
     F = W1.shape[0]
-    step = FfnStep(T, D, F, mode, X.device, keep_dense, M)
+    step = FfnStep(T, D, F, mode, X.device, keep_dense, M, unfused)
     out = step(X, W1, W2, b1, dY)
     return out, step
 

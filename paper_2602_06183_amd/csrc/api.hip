@@ -47,14 +47,21 @@ struct FullLayout {
     size_t w1_vblk, w1_mblk, w2t_vblk, w2t_mblk, x_blk, xt_blk, dy_blk, dyt_blk, w2_blk, w1t_blk, a24_vblk, a24_mblk, at_blk, kmask, total;
 };
 
+// Blocks of M = 16, 32, 64 columns take the fused path (V:N:M epilogues inside eqs. (1), (4), gathered-row eqs. (3), (7)) when the
+// gathered-row kernel covers the shape and the caller does not ask for the unfused reference path.
+bool fused_wide(const sffn_cfg* c) {
+    return c->M != 8 && !(c->flags & SFFN_FLAG_UNFUSED) && vnm_spmm_gather_ok(c->T, c->D, c->F, c->M) && c->F * c->D * 2 < ((int64_t)1 << 32);
+}
+
 // E = number of experts (1 for the plain step): every weight-shaped tensor holds E matrices back to back.
 bool make_layout(const sffn_cfg* c, FullLayout* L, int n_experts = 1) {
     if (!c || !mult64(c->T) || !mult64(c->D) || !mult64(c->F) || n_experts < 1) return false;
     if (!vnm_ok(c->V, c->M)) return false;
     const size_t M = (size_t)c->M;                                    // wider blocks: smaller packed tensors, unfused path
     if (c->F % (2 * M) != 0) return false;
-    // the dense y1 / dy2 exist only where a kernel stores them: on request in the fused M = 8 step, always in the unfused one
-    const bool dense = (c->flags & SFFN_FLAG_KEEP_DENSE) || M != 8;
+    // the dense y1 / dy2 exist only where a kernel stores them: on request in the fused step, always in the unfused one
+    const bool fused = M == 8 || fused_wide(c);
+    const bool dense = (c->flags & SFFN_FLAG_KEEP_DENSE) || !fused;
     const size_t T = c->T, D = c->D, F = (size_t)c->F * n_experts;   // F only sizes weight-shaped tensors below ...
     const size_t TF = T * (size_t)c->F;                               // ... token x hidden tensors use TF
     size_t off = 0;
@@ -65,7 +72,8 @@ bool make_layout(const sffn_cfg* c, FullLayout* L, int n_experts = 1) {
     L->pub.y2_vals = take(TF * 4 / M);  L->pub.y2_meta = take(TF / (2 * M));   L->pub.colidx = take(TF / 64 / M * 4);
     L->pub.dy2 = take(dense ? TF * 2 : 0);
     L->pub.dy1_vals = take(TF * 4 / M);
-    L->pub.y1_kept = take(M == 8 ? TF / 2 : 0);
+    L->pub.y1_kept_bytes = fused ? TF * 4 / M : 0;
+    L->pub.y1_kept = take(L->pub.y1_kept_bytes);
     L->w1_vblk = take(F * D);              L->w1_mblk = take(F * D / 8);
     L->w2t_vblk = take(F * D);             L->w2t_mblk = take(F * D / 8);
     L->x_blk = take(T * D * 2);            L->xt_blk = take(D * T * 2);
@@ -612,7 +620,8 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     REQUIRE(n_experts >= 1 && n_experts <= GemmGroup::kMaxExperts, SFFN_EINVAL, "ffn_sparse_step_grouped: n_experts must be in 1..64");
     REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "ffn_sparse_step: only V=64 with M in {8, 16, 32, 64} is built");
     REQUIRE(make_layout(cfg, &L, n_experts), SFFN_EINVAL, "ffn_sparse_step: T, D, F must be positive multiples of 64 and F a multiple of 2 M");
-    REQUIRE(cfg->M == 8 || (seg == nullptr && n_experts == 1), SFFN_EUNSUPPORTED, "ffn_sparse_step_grouped: only M=8 is built");
+    REQUIRE(cfg->M == 8 || fused_wide(cfg) || (seg == nullptr && n_experts == 1), SFFN_EUNSUPPORTED,
+            "ffn_sparse_step_grouped: blocks of 16 / 32 / 64 columns need 4 F / M to be a multiple of 64 and at most 7168 (and no SFFN_FLAG_UNFUSED)");
     REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_sparse_step: unknown mode");
     REQUIRE(aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(b1) && aligned16(dY) && aligned16(Y3) && aligned16(dX) &&
                 aligned16(dW1) && aligned16(dW2) && aligned16(workspace),
@@ -649,6 +658,43 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     uint8_t* kmask = ws + L.kmask;
     uint16_t* ykept = (uint16_t*)(ws + L.pub.y1_kept);
     const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
+    if (fused_wide(cfg)) {
+        // Blocks of M = 16, 32, 64 columns (Table 5), fused like the M = 8 step: eq. (2) + compression in the epilogue of eq. (1), eq. (6)
+        // in the epilogue of eq. (4) (the dense y1 / dy2 stay in LDS), eqs. (3), (7) on the kept rows of W2.T / W1 only (the pruning
+        // pass of W2 also writes W2.T), eqs. (5), (8) on the dense transposed activation that the epilogues write.  10 launches.
+        const int M = cfg->M, logM = M == 16 ? 4 : M == 32 ? 5 : 6;
+        GemmGroup g_packed = g, g_rows = g, g_wgrad = g;
+        g_packed.role = 1; g_packed.a_stride = F * D / 2; g_packed.m_stride = F * D / 8; g_packed.bias_stride = F;
+        g_rows.role = 0;   g_rows.b_stride = F * D;
+        g_wgrad.role = 2;  g_wgrad.out_stride = D * F;
+        const GemmGroup* gp = g.n ? &g_packed : nullptr;
+        const GemmGroup* gr = g.n ? &g_rows : nullptr;
+        const GemmGroup* gw = g.n ? &g_wgrad : nullptr;
+        uint16_t* xt = xtb;                              // X.T and dY.T [D, T], row-major here
+        uint16_t* dyt = dytb;
+        uint16_t* w2t = w1tb;                            // W2.T [F, D] per expert
+        uint16_t* at = atb;                              // dense transposed activation [F, T]
+        if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
+        STAGE(launch_transpose(X, T, D, D, xt, 0, xb, s), "step/X.T");
+        STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, w1v, w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
+        {
+            VnmEpilogue ep;
+            ep.mode = 5; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = y2v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept; ep.at = at;
+            STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s, gp), "step/y1+sqrelu_vnm_compress");         // eqs. (1), (2), Section 2.3
+        }
+        STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, w2v, w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
+        STAGE(launch_vnm_spmm_gather(y2v, y2m, cix, w2t, D, T, D, F, M, Y3, D, s, gr), "step/y3");                              // eq. (3)
+        STAGE(launch_transpose(dY, T, D, D, dyt, 0, dyb, s), "step/dY.T");
+        STAGE(launch_gemm_nt(0, at, nullptr, dyt, nullptr, F, D, T, 1, dW2, F, s, gw), "step/dW2");                             // eq. (5)
+        {
+            VnmEpilogue ep;
+            ep.mode = 6; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept; ep.at = at;
+            STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, ep, s, gp), "step/dy2+dsqrelu_vnm");         // eqs. (4), (6)
+        }
+        STAGE(launch_vnm_spmm_gather(dy1v, y2m, cix, W1, D, T, D, F, M, dX, D, s, gr), "step/dX");                              // eq. (7), dense W1 as is
+        STAGE(launch_gemm_nt(0, at, nullptr, xt, nullptr, F, D, T, 0, dW1, D, s, gw), "step/dW1");                              // eq. (8)
+        return SFFN_OK;
+    }
     if (cfg->M != 8) {
         // Wider blocks (Table 5): the same Alg. 1 / Alg. 2 without the fused epilogues.  Eqs. (1), (4) run on the blocked
         // operands like the M = 8 step but only store the dense y1 / dy2 (they are what the stand-alone eq. (2) / eq. (6)

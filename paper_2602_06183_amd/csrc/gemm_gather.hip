@@ -39,7 +39,7 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 __global__ void __launch_bounds__(256) vnm_spmm_gather_kernel(const uint16_t* __restrict__ a_vals, const uint8_t* __restrict__ a_meta,
                                                              const uint8_t* __restrict__ colidx, const uint16_t* __restrict__ Wk,
                                                              int ldw, int N, int Kc, int logM, int nblk_tok, int tiles_n,
-                                                             uint16_t* __restrict__ out, int64_t ldo) {
+                                                             uint16_t* __restrict__ out, int64_t ldo, GemmGroup grp) {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kGStages * kGStage];
     __shared__ __attribute__((aligned(16))) unsigned char cix[kGMaxKc];
 
@@ -56,6 +56,11 @@ __global__ void __launch_bounds__(256) vnm_spmm_gather_kernel(const uint16_t* __
     }
     const int tn = L / nblk_tok, tb = L - tn * nblk_tok;
     const int t0 = tb * 64, n0 = tn * 256;
+    if (grp.n) {                                         // grouped form: the token block's segment names the expert whose matrix it meets
+        int e = 0;
+        while (e + 1 < grp.n && t0 >= grp.seg[e + 1]) ++e;
+        Wk += e * grp.b_stride;
+    }
 
     // ---- column offsets of this token block -> LDS ------------------------------------------------------------
     {
@@ -225,12 +230,14 @@ bool vnm_spmm_gather_ok(int64_t T, int64_t N, int64_t F, int M) {
 }
 
 hipError_t launch_vnm_spmm_gather(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* colidx, const uint16_t* Wk, int64_t ldw,
-                                  int64_t T, int64_t N, int64_t F, int M, uint16_t* out, int64_t ldo, hipStream_t s) {
+                                  int64_t T, int64_t N, int64_t F, int M, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp) {
     if (!vnm_spmm_gather_ok(T, N, F, M) || ldw < N || F * ldw * 2 >= ((int64_t)1 << 32)) return hipErrorInvalidValue;
+    const GemmGroup g = grp ? *grp : GemmGroup();
+    if (g.n && (g.role != 0 || g.seg_dev || g.n > GemmGroup::kMaxExperts)) return hipErrorInvalidValue;
     const int Kc = (int)(4 * F / M), logM = M == 8 ? 3 : M == 16 ? 4 : M == 32 ? 5 : 6;
     const int nblk_tok = (int)(T / 64), tiles_n = (int)((N + 255) / 256);
     hipLaunchKernelGGL(vnm_spmm_gather_kernel, dim3((unsigned)(nblk_tok * tiles_n)), dim3(256), 0, s, a_vals, a_meta, colidx, Wk, (int)ldw, (int)N,
-                       Kc, logM, nblk_tok, tiles_n, out, ldo);
+                       Kc, logM, nblk_tok, tiles_n, out, ldo, g);
     return hipGetLastError();
 }
 

@@ -47,6 +47,10 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                                                         int Ra, int Rb, int K, uint16_t* __restrict__ out, int64_t ldo,
                                                         int tiles_m, int tiles_n, VnmEpilogue ep, GemmGroup grp, float alpha = 1.0f) {
     static_assert(EPI == 0 || (SPARSE && OUT_I_CONTIG && BLOCKED), "the V:N:M epilogues belong to the 2:4-weight GEMMs of the fused step");
+    // EPI 16 + log2(M) / 32 + log2(M): the forward (eq. (2) + compression) / backward (eq. (6)) epilogue for blocks of M = 16, 32, 64 columns
+    constexpr bool GEN_F = EPI >= 16 && EPI < 32, GEN_B = EPI >= 32;
+    constexpr int LOGM = (GEN_F || GEN_B) ? (EPI & 15) : 3;
+    static_assert(!(GEN_F || GEN_B) || (LOGM >= 4 && LOGM <= 6), "wide V:N:M blocks: M = 16, 32 or 64");
     static_assert(!FP8 || (SPARSE && !BLOCKED && EPI == 0), "fp8 operands: structured-sparse kernel on row-major operands");
     constexpr bool blocked = BLOCKED;       // operands in the blocked layout of common.hpp (fused step) or row-major (stand-alone entry points)
     using C = Cfg<SPARSE, FP8>;
@@ -310,7 +314,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         // through LDS as [j][i] (two halves of 64 i) so that HBM sees 128-byte row segments instead of
         // 16-byte ones; the bias (indexed by i) is added before the single rounding to bf16.
         constexpr int EP = 64 * 2 + 16;
-        constexpr int WAVE_LDS = (EPI != 0) ? (WN + 32) * EP : WN * EP;  // EPI: second tile (32 compact rows) for the transposed output
+        // EPI: second tile for the transposed output (32 compact rows; 64 dense rows for the wide-block epilogues)
+        constexpr int WAVE_LDS = (GEN_F || GEN_B) ? (WN + 64) * EP : (EPI != 0) ? (WN + 32) * EP : WN * EP;
         unsigned char* scratch = smem + wave * WAVE_LDS;
         static_assert(8 * WAVE_LDS <= C::NSTAGE * C::STAGE, "epilogue scratch must fit in the main-loop LDS");
         unsigned char* ttile = scratch + WN * EP;
@@ -319,6 +324,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         const int t0 = j0 + wn * WN;
         const int nblk = Ra >> 3;
         const int64_t F = Ra;
+        uint32_t nib_h0 = 0;                                  // M = 64: the metadata nibble of the first half waits for the second's
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int f0 = i0 + wm * WM + h * 64;
@@ -361,10 +367,11 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         *reinterpret_cast<uint2*>(scratch + (b * 32 + l32) * EP + il * 2) =
                             tok_ok[b] ? make_uint2(f2bf2(v0, v1), f2bf2(v2, v3)) : make_uint2(0u, 0u);
                     }
-            if (EPI == 1 || EPI == 2) {
+            if (EPI == 1 || EPI == 2 || GEN_F || GEN_B) {
+                constexpr int TROWS = (GEN_F || GEN_B) ? 64 : 32;
 #pragma unroll
-                for (int q = 0; q < (32 * EP + 1023) / 1024; ++q)
-                    if ((q * 64 + lane) * 16 < 32 * EP) *reinterpret_cast<uint4*>(ttile + (q * 64 + lane) * 16) = make_uint4(0, 0, 0, 0);
+                for (int q = 0; q < (TROWS * EP + 1023) / 1024; ++q)
+                    if ((q * 64 + lane) * 16 < TROWS * EP) *reinterpret_cast<uint4*>(ttile + (q * 64 + lane) * 16) = make_uint4(0, 0, 0, 0);
             }
             wave_lds_sync();
             if (EPI == 0 || ep.store_dense) {
@@ -431,6 +438,106 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                     if (valid && t0 + t < Rb) {
                         *reinterpret_cast<uint32_t*>(ep.vals + (int64_t)(t0 + t) * (F / 2) + (f0 >> 1) + 2 * g) = v;
                         *reinterpret_cast<uint32_t*>(ep.v24 + blk_off(t0 + t, (f0 >> 1) + 2 * g, F / 64)) = v;
+                    }
+                }
+            }
+            if (GEN_F || GEN_B) {
+                // Blocks of M = 16 / 32 / 64 columns (Table 5): the wave's 64 tokens x 64 hidden units hold NB = 64 / M whole blocks.
+                // Lane = column for the ordered scores and the ranking inside a block; lane = (token, block) for the per-row 2:4 choice,
+                // block = lane % NB in every sweep.  The survivors also go, scattered to their hidden units, into a zeroed [64 units x
+                // 64 tokens] tile that leaves as rows of the dense transposed activation [F, T] (operand of the weight-gradient GEMM).
+                constexpr int M = 1 << LOGM, NB = 64 >> LOGM;
+                const int64_t nblkM = F >> LOGM, blk0 = f0 >> LOGM;
+                const int b = lane & (NB - 1);
+                uint32_t cb;                                              // the four kept column offsets of block b
+                if (GEN_F) {
+                    float sc = 0.0f;
+#pragma unroll 8
+                    for (int r = 0; r < WN; ++r)
+                        sc = sc + __uint_as_float(sqrelu_hi(*reinterpret_cast<const uint16_t*>(scratch + r * EP + lane * 2)));
+                    const int c = lane & (M - 1), base = lane - c;
+                    int rank = 0;
+#pragma unroll 8
+                    for (int k = 0; k < M; ++k) {
+                        const float o = __shfl(sc, base + k, 64);
+                        rank += (k < c) ? (o >= sc) : ((k > c) ? (o > sc) : 0);
+                    }
+                    const unsigned long long kept = __ballot(rank < 4);
+                    unsigned long long bits = (M == 64) ? kept : ((kept >> base) & ((1ull << (M & 63)) - 1ull));
+                    uint32_t cw = 0;
+#pragma unroll
+                    for (int n = 0; n < 4; ++n) {
+                        cw |= (uint32_t)__builtin_ctzll(bits) << (8 * n);
+                        bits &= bits - 1ull;
+                    }
+                    if (valid && c == 0) *reinterpret_cast<uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblkM + blk0 + (lane >> LOGM)) * 4) = cw;
+                    cb = (uint32_t)__shfl((int)cw, b << LOGM, 64);
+                } else {
+                    cb = valid ? *reinterpret_cast<const uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblkM + blk0 + b) * 4) : 0x03020100u;
+                }
+                const uint32_t q0 = (cb & 0xFFu) * 2, q1 = ((cb >> 8) & 0xFFu) * 2, q2 = ((cb >> 16) & 0xFFu) * 2, q3 = (cb >> 24) * 2;
+                const int r_lane = lane >> (6 - LOGM);                    // token of sweep 0; sweep s adds s * M
+                uint32_t* vals_p = reinterpret_cast<uint32_t*>(ep.vals) + (int64_t)(t0 + r_lane) * (F >> LOGM) + blk0 + b;
+                uint32_t* kept_p = reinterpret_cast<uint32_t*>(ep.ykept) + ((((int64_t)(t0 >> 6) * (F >> 6) + (f0 >> 6)) << 6) + r_lane) * NB + b;
+                uint8_t* meta_p = ep.meta + (int64_t)(t0 + r_lane) * (F >> (LOGM + 1)) + ((blk0 + b) >> 1);
+                uint32_t pre_m[NB], pre_y[NB];
+                if (GEN_B && valid) {
+#pragma unroll
+                    for (int sw = 0; sw < NB; ++sw) {
+                        pre_m[sw] = meta_p[(int64_t)sw * M * (F >> (LOGM + 1))];
+                        pre_y[sw] = kept_p[sw * M * NB];
+                    }
+                }
+                if (valid) {
+#pragma unroll
+                    for (int sw = 0; sw < NB; ++sw) {
+                        const int t = r_lane + sw * M;
+                        const unsigned char* row = scratch + t * EP + (b << LOGM) * 2;
+                        uint32_t v, nib;
+                        if (GEN_F) {
+                            const uint32_t y0 = *reinterpret_cast<const uint16_t*>(row + q0);
+                            const uint32_t y1 = *reinterpret_cast<const uint16_t*>(row + q1);
+                            const uint32_t y2 = *reinterpret_cast<const uint16_t*>(row + q2);
+                            const uint32_t y3 = *reinterpret_cast<const uint16_t*>(row + q3);
+                            v = select24<false>(sqrelu16(y0), sqrelu16(y1), sqrelu16(y2), sqrelu16(y3), nib);
+                            const uint32_t p0 = nib & 3u, p1 = nib >> 2;
+                            const uint32_t k0 = (p0 == 0) ? y0 : (p0 == 1) ? y1 : y2;
+                            const uint32_t k1 = (p1 == 3) ? y3 : (p1 == 2) ? y2 : y1;
+                            vals_p[(int64_t)sw * M * (F >> LOGM)] = v;
+                            kept_p[sw * M * NB] = k0 | (k1 << 16);
+                            // two blocks share a metadata byte: neighbours in the lane order (M = 16, 32) or the two halves of the wave tile (M = 64)
+                            if (LOGM == 4) {
+                                uint32_t mw = nib | (row_shl<1>(nib) << 4);
+                                mw |= row_shl<2>(mw) << 8;
+                                if (b == 0) *reinterpret_cast<uint16_t*>(meta_p + (int64_t)sw * M * (F >> (LOGM + 1))) = (uint16_t)mw;
+                            } else if (LOGM == 5) {
+                                const uint32_t mw = nib | (row_shl<1>(nib) << 4);
+                                if (b == 0) meta_p[(int64_t)sw * M * (F >> (LOGM + 1))] = (uint8_t)mw;
+                            } else {
+                                if (h == 0) nib_h0 = nib;
+                                else meta_p[0] = (uint8_t)(nib_h0 | (nib << 4));
+                            }
+                        } else {
+                            const uint32_t yk = pre_y[sw];
+                            nib = (pre_m[sw] >> (4 * ((blk0 + b) & 1))) & 0xFu;
+                            const uint32_t o0 = (cb >> (8 * (nib & 3u))) & 0xFFu, o1 = (cb >> (8 * (nib >> 2))) & 0xFFu;
+                            const float d0 = bf2f(*reinterpret_cast<const uint16_t*>(row + o0 * 2));
+                            const float d1 = bf2f(*reinterpret_cast<const uint16_t*>(row + o1 * 2));
+                            const float ya = bf2f(yk & 0xFFFFu), yb = bf2f(yk >> 16);
+                            v = f2bf2(2.0f * d0 * (ya > 0.0f ? ya : 0.0f), 2.0f * d1 * (yb > 0.0f ? yb : 0.0f));
+                            vals_p[(int64_t)sw * M * (F >> LOGM)] = v;
+                        }
+                        const uint32_t o0 = (cb >> (8 * (nib & 3u))) & 0xFFu, o1 = (cb >> (8 * (nib >> 2))) & 0xFFu;
+                        *reinterpret_cast<uint16_t*>(ttile + ((b << LOGM) + o0) * EP + t * 2) = (uint16_t)(v & 0xFFFFu);
+                        *reinterpret_cast<uint16_t*>(ttile + ((b << LOGM) + o1) * EP + t * 2) = (uint16_t)(v >> 16);
+                    }
+                }
+                wave_lds_sync();
+                if (valid) {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {          // 64 hidden units x 64 tokens: rows of 128 bytes of the [F, tokens] matrix
+                        const int fr = q * 8 + (lane >> 3), tc = (lane & 7) * 8;
+                        *reinterpret_cast<uint4*>(ep.at + (int64_t)(f0 + fr) * tok_ld + t0 + tc) = *reinterpret_cast<const uint4*>(ttile + fr * EP + tc * 2);
                     }
                 }
             }
@@ -639,6 +746,15 @@ hipError_t launch_gemm_vnm_epilogue(const uint16_t* a_vals, const uint8_t* a_met
     const unsigned tiles = grid_tiles(tiles_m, tiles_n, g);
     if (tiles == 0) return hipSuccess;
     dim3 grid(tiles);
+#define SFFN_EPI(E) hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, E, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F, \
+                                      tiles_m, tiles_n, ep, g)
+    if (ep.mode == 5 || ep.mode == 6) {     // wide blocks: forward / backward epilogue for M = 16, 32, 64
+        if (ep.logM < 4 || ep.logM > 6) return hipErrorInvalidValue;
+        if (ep.mode == 5) { if (ep.logM == 4) SFFN_EPI(20); else if (ep.logM == 5) SFFN_EPI(21); else SFFN_EPI(22); }
+        else              { if (ep.logM == 4) SFFN_EPI(36); else if (ep.logM == 5) SFFN_EPI(37); else SFFN_EPI(38); }
+        return hipGetLastError();
+    }
+#undef SFFN_EPI
     if (ep.mode == 0)       // no V:N:M work: the dense output only
         hipLaunchKernelGGL((gemm_nt_v2_kernel<true, true, 0, true>), grid, dim3(512), 0, s, a_vals, a_meta, B, bias, (int)F, (int)T, (int)K, out, F,
                            tiles_m, tiles_n, ep, g);

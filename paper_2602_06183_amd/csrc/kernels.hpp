@@ -29,6 +29,9 @@ struct VnmEpilogue {
     //        compact columns: outputs vals, meta; padding rows (perm < 0) come out as zeros; `out` = y1c [rows, F] if store_dense.
     // mode 4 (the same experts, backward): the tile of dy2c meets (meta, ykept = the stored y1c [rows, F]) and becomes dy1 in y2's
     //        slots: outputs vals (canonical) and v24 (the same, blocked); `out` = dy2c if store_dense.
+    // mode 5 / 6 (blocks of M = 2^logM = 16, 32, 64 columns, Table 5): as modes 1 / 2 with outputs vals, meta, colidx (mode 5), ykept
+    //        ([T/64][F/64][64 tokens][64/M blocks] pairs) and `at` = the DENSE transposed activation [F, tokens] row-major; no v24 / m24
+    //        (eqs. (3), (7) gather the kept rows of the dense operand from the canonical arrays).
     const int32_t* perm = nullptr;
     int logM = 3;
 };
@@ -67,7 +70,8 @@ hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uin
 // batch > 1 (trans = 1 only): `batch` matrices of the same shape, consecutive in every argument.
 hipError_t launch_prune24_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
                                uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream, int batch = 1,
-                               int cluster_M = 0);   // cluster_M (trans = 0): rows come out expert-major, see prune24.hip
+                               int cluster_M = 0,    // cluster_M (trans = 0): rows come out expert-major, see prune24.hip
+                               uint16_t* src_t = nullptr);   // trans = 1: also the unpruned transposed source [R, K] row-major
 // vnm_general.hip: the stand-alone compressor for M in {8, 16, 32, 64}, and eq. (6) / 2:4 re-expression / transposed expansion for M in {16, 32, 64}.
 hipError_t launch_sqrelu_vnm_compress_m(const uint16_t* y1, int64_t T, int64_t F, int M, uint16_t* vals, uint8_t* meta, uint8_t* colidx,
                                         hipStream_t s);
@@ -81,8 +85,9 @@ hipError_t launch_vnm_expand_t_m(const uint16_t* vals, const uint8_t* meta, cons
 // out[t, n] = sum over the kept columns f of A[t, f] * Wk[f, n]; Wk = [F, ldw] (contraction index = row).
 // vnm_spmm_gather_ok: shapes the kernel covers (4 F / M a multiple of 64 and at most 7168); others take the plain-2:4 route.
 bool vnm_spmm_gather_ok(int64_t T, int64_t N, int64_t F, int M);
+// grp (role 0, host segment table): the token blocks of segment e take expert e's matrix Wk + e * b_stride.
 hipError_t launch_vnm_spmm_gather(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* colidx, const uint16_t* Wk, int64_t ldw,
-                                  int64_t T, int64_t N, int64_t F, int M, uint16_t* out, int64_t ldo, hipStream_t s);
+                                  int64_t T, int64_t N, int64_t F, int M, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 hipError_t launch_vnm_to_24(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
                             uint16_t* vals24, uint8_t* meta24, hipStream_t s);
 hipError_t launch_vnm_expand_t(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,

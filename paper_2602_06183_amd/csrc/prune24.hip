@@ -45,7 +45,7 @@ template <bool SOFT>
 __global__ void __launch_bounds__(256) prune24_cols_kernel(const uint16_t* __restrict__ src, int64_t R, int K, int64_t ld,
                                                           uint16_t* __restrict__ vals, uint8_t* __restrict__ meta,
                                                           uint16_t* __restrict__ vblk, uint8_t* __restrict__ mblk,
-                                                          uint16_t* __restrict__ src_blk) {
+                                                          uint16_t* __restrict__ src_blk, uint16_t* __restrict__ src_t = nullptr) {
     constexpr int TK = 128, TR = 64, PITCH = TR + 8;
     __shared__ __attribute__((aligned(16))) uint16_t tile[TK * PITCH];
     const int64_t r0 = (int64_t)blockIdx.x * TR;
@@ -56,6 +56,7 @@ __global__ void __launch_bounds__(256) prune24_cols_kernel(const uint16_t* __res
         src += m; vals += m / 2; meta += m / 8;
         if (vblk) { vblk += m / 2; mblk += m / 8; }
         if (src_blk) src_blk += m;
+        if (src_t) src_t += m;
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -72,6 +73,19 @@ __global__ void __launch_bounds__(256) prune24_cols_kernel(const uint16_t* __res
             const int kr = (bk >> 1) * 16 + (l >> 2), rc = (bk & 1) * 32 + (l & 3) * 8;
             if (k0 + kr < K)
                 *reinterpret_cast<uint4*>(src_blk + blk_off(k0 + kr, r0 + rc, R / 32)) = *reinterpret_cast<const uint4*>(&tile[kr * PITCH + rc]);
+        }
+    }
+    if (src_t) {        // the unpruned transposed tile: logical rows r (64) x k (128) -> [R, K] row-major, 16 bytes per thread and pass
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = tid + 256 * i, tr = e & 63, ks = e >> 6;       // row r0 + tr, k segment of 8 starting at 8 ks
+            if (k0 + 8 * ks < K) {
+                uint32_t w[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    w[j] = tile[(8 * ks + 2 * j) * PITCH + tr] | ((uint32_t)tile[(8 * ks + 2 * j + 1) * PITCH + tr] << 16);
+                *reinterpret_cast<uint4*>(src_t + (r0 + tr) * K + k0 + 8 * ks) = make_uint4(w[0], w[1], w[2], w[3]);
+            }
         }
     }
     const int rr = tid % 64, q = tid / 64;
@@ -152,7 +166,8 @@ hipError_t launch_prune24(const uint16_t* src, int64_t R, int64_t K, int64_t ld,
 }
 
 hipError_t launch_prune24_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, uint16_t* vals,
-                               uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream, int batch, int cluster_M) {
+                               uint8_t* meta, uint16_t* vblk, uint8_t* mblk, uint16_t* src_blk, hipStream_t stream, int batch, int cluster_M,
+                               uint16_t* src_t) {
     if (batch > 1 && (!trans || ld != R)) return hipErrorInvalidValue;
     if (cluster_M && (trans || (cluster_M != 8 && cluster_M != 16 && cluster_M != 32 && cluster_M != 64) || R % cluster_M)) return hipErrorInvalidValue;
     if (!trans) {
@@ -163,8 +178,8 @@ hipError_t launch_prune24_step(const uint16_t* src, int64_t R, int64_t K, int64_
         else           hipLaunchKernelGGL((prune24_rows_step_kernel<true>), grid, dim3(256), 0, stream, src, (int)K, ld, vals, meta, vblk, mblk, logM, Kc);
     } else {
         dim3 grid((unsigned)(R / 64), (unsigned)((K + 127) / 128), (unsigned)batch);
-        if (mode == 0) hipLaunchKernelGGL((prune24_cols_kernel<false>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta, vblk, mblk, src_blk);
-        else           hipLaunchKernelGGL((prune24_cols_kernel<true>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta, vblk, mblk, src_blk);
+        if (mode == 0) hipLaunchKernelGGL((prune24_cols_kernel<false>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta, vblk, mblk, src_blk, src_t);
+        else           hipLaunchKernelGGL((prune24_cols_kernel<true>), grid, dim3(256), 0, stream, src, R, (int)K, ld, vals, meta, vblk, mblk, src_blk, src_t);
     }
     return hipGetLastError();
 }

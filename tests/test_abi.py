@@ -138,7 +138,12 @@ def test_workspace_has_no_dense_activation_unless_it_is_stored():
     assert lay["y2_vals"] == lay["y1"] and lay["dy1_vals"] == lay["dy2"]            # empty regions
     layk = sffn.workspace_layout(T, D, F, keep_dense=True)
     assert layk["y2_vals"] - layk["y1"] == 2 * T * F and layk["dy1_vals"] - layk["dy2"] == 2 * T * F
-    assert sffn.workspace_bytes(T, D, F, M=16) == sffn.workspace_bytes(T, D, F, M=16, keep_dense=True) > 0
+    # blocks of 16 columns: fused like M = 8 when the gathered-row kernel covers the shape (4 F / M a multiple of 64), else / on request unfused
+    assert sffn.workspace_bytes(T, D, F, M=16, keep_dense=True) - sffn.workspace_bytes(T, D, F, M=16) == 2 * 2 * T * F
+    assert sffn.workspace_bytes(T, D, F, M=16, unfused=True) == sffn.workspace_bytes(T, D, F, M=16, keep_dense=True, unfused=True) > 0
+    assert sffn.workspace_bytes(T, D, 640, M=16) == sffn.workspace_bytes(T, D, 640, M=16, keep_dense=True) > 0
+    assert sffn.workspace_layout(T, D, F, M=16)["y1_kept_bytes"] == T * 2 * F // 16 * 2 and sffn.workspace_layout(T, D, F, M=16, unfused=True)["y1_kept_bytes"] == 0
+    assert sffn.workspace_layout(T, D, F)["y1_kept_bytes"] == T * F // 4 * 2
     lib = sffn.load()
     for M in (0, 4, 12, 128):
         c = binding._Cfg(T, D, F, 64, M, 0, 0)

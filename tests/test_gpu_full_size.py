@@ -182,16 +182,23 @@ def test_full_size_grouped_step():
 
 @pytest.mark.parametrize("M", [16, 64])
 def test_full_size_wide_block_step(M):
-    """Table 5's wider blocks at the 1B shape, as bench.py --M times it: eqs. (3), (7) on the gathered-row kernel.
+    """Table 5's wider blocks at the 1B shape, as bench.py --M times it: fused epilogues, eqs. (3), (7) on the gathered-row kernel.
     Compressors bit-exact on sampled token blocks, GEMM outputs on sampled rows / column blocks, teacher-forced."""
     T, D, F = CONFIGS["1b"]
     inp = make_ffn_inputs(T, D, F, seed=0)
     dev = {k: to_dev(v) for k, v in inp.items()}
-    step = sffn.FfnStep(T, D, F, sffn.MODE_HARD, M=M)
+    fast = sffn.FfnStep(T, D, F, sffn.MODE_HARD, M=M)                   # what bench.py --M times: fused, no dense y1 / dy2
+    outs_fast = [to_bits(t).copy() for t in fast(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    packed_fast = [to_bits(fast.saved()[k]).copy() for k in ("y2_vals", "y2_meta", "colidx", "dy1_vals", "y1_kept")]
+    del fast
+    torch.cuda.empty_cache()
+    step = sffn.FfnStep(T, D, F, sffn.MODE_HARD, M=M, keep_dense=True)
     outs = step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
     torch.cuda.synchronize()
     Y3, dX, dW1, dW2 = (to_bits(t) for t in outs)
     sv = {k: to_bits(v) for k, v in step.saved().items()}
+    assert all(np.array_equal(a, b) for a, b in zip(outs_fast, (Y3, dX, dW1, dW2)))
+    assert all(np.array_equal(a, sv[k]) for a, k in zip(packed_fast, ("y2_vals", "y2_meta", "colidx", "dy1_vals", "y1_kept")))
     y1, dy2, yv, ym, yc, dv = (sv[k] for k in ("y1", "dy2", "y2_vals", "y2_meta", "colidx", "dy1_vals"))
     rng = np.random.default_rng(1000 + M)
 

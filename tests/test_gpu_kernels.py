@@ -184,12 +184,22 @@ def _check_step_against_oracle(inp, s, outs, mode):
 
 
 def _check_wide_step_against_oracle(inp, s, outs, mode, M):
-    """The same teacher-forced chain for V:2:M blocks wider than 8 (no y1_kept in that path)."""
+    """The same teacher-forced chain for V:2:M blocks wider than 8 (y1_kept only on the fused path)."""
     rv, rm = oracle.prune24_compress(inp["W1"], mode)
     assert np.array_equal(s["w1_vals"], rv) and np.array_equal(s["w1_meta"], rm)
     assert_gemm_close(s["y1"], oracle.spmm24(inp["X"], rv, rm, inp["b1"]), "y1")
     yv, ym, yc = oracle.sqrelu_vnm_compress(s["y1"], 64, M)
     assert np.array_equal(s["colidx"], yc) and np.array_equal(s["y2_meta"], ym) and np.array_equal(s["y2_vals"], yv)
+    if "y1_kept" in s:       # y1 at the kept slots, stored in runs of 64 tokens x (64 / M) column blocks
+        T, F = s["y1"].shape
+        ones = np.arange(1, yv.size + 1, dtype=np.uint32).reshape(yv.shape)
+        slot_of = oracle.vnm_decompress((ones & 0xFFFF).astype(np.uint16), ym, yc, 64, M).astype(np.int64) \
+            + (oracle.vnm_decompress((ones >> 16).astype(np.uint16), ym, yc, 64, M).astype(np.int64) << 16)
+        want_kept = np.zeros(yv.size, dtype=np.uint16)
+        tt, ff = np.nonzero(slot_of)
+        want_kept[slot_of[tt, ff] - 1] = s["y1"][tt, ff]
+        want_kept = want_kept.reshape(T // 64, 64, F // 64, 64 // M, 2).transpose(0, 2, 1, 3, 4)
+        assert np.array_equal(np.asarray(s["y1_kept"]).reshape(-1), want_kept.reshape(-1))
     assert_gemm_close(outs["Y3"], oracle.vnm_spmm(yv, ym, yc, inp["W2"], 0, 64, M), "y3")
     rv2, rm2 = oracle.prune24_compress(np.ascontiguousarray(inp["W2"].T), mode)
     assert np.array_equal(s["w2t_vals"], rv2) and np.array_equal(s["w2t_meta"], rm2)
@@ -392,7 +402,8 @@ def test_vnm_spmm_gathered_rows(M, T, F, N):
                                       (16, sffn.MODE_SOFT, 1024), (32, sffn.MODE_HARD, 1024), (64, sffn.MODE_SOFT, 1024)])
 def test_ffn_sparse_step_wide_blocks(M, mode, F):
     """ffn_sparse_step with V:2:M blocks of 16 / 32 / 64 columns, teacher-forced against the oracle stage by stage
-    (F = 640: eqs. (3), (7) on the plain-2:4 route; F = 1024: on the gathered-row kernel)."""
+    (F = 640: the unfused path, eqs. (3), (7) on the plain-2:4 route; F = 1024: the fused path, eqs. (2), (6) in the GEMM
+    epilogues and eqs. (3), (7) on the gathered-row kernel)."""
     T, D = 320, 192
     inp = make_ffn_inputs(T, D, F, seed=7, zero_fraction=0.75)
     dev = {k: to_dev(v) for k, v in inp.items()}
@@ -403,6 +414,65 @@ def test_ffn_sparse_step_wide_blocks(M, mode, F):
     _check_wide_step_against_oracle(inp, s, outs, mode, M)
     density = np.mean(oracle.vnm_decompress(s["y2_vals"], s["y2_meta"], s["colidx"], 64, M) != 0)
     assert density <= 2.0 / M + 1e-9                       # Table 5: sparsity at least 1 - N / M
+    assert ("y1_kept" in s) == (F == 1024)
+
+
+WIDE_KEYS = ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta", "y2_vals", "y2_meta", "colidx", "dy1_vals")
+
+
+@pytest.mark.parametrize("M", [16, 32, 64])
+@pytest.mark.parametrize("mode,zf", [(sffn.MODE_HARD, 0.50), (sffn.MODE_SOFT, 0.90)])
+def test_wide_block_step_fused_is_bit_identical_to_unfused(M, mode, zf):
+    """Blocks of 16 / 32 / 64 columns: the fused step (V:N:M epilogues, no dense y1 / dy2 in HBM) against the unfused path with its
+    separate compress / eq. (6) kernels: every output and every packed tensor the same bits; so is the fused run that also stores
+    y1 / dy2, and those equal the unfused path's."""
+    T, D, F = 448, 192, 1024
+    inp = make_ffn_inputs(T, D, F, seed=11, zero_fraction=zf)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    res = {}
+    for name, kw in (("fused", dict()), ("fused+dense", dict(keep_dense=True)), ("unfused", dict(unfused=True))):
+        step = sffn.FfnStep(T, D, F, mode, M=M, **kw)
+        outs = [to_bits(t).copy() for t in step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+        sv = step.saved()
+        res[name] = outs + [to_bits(sv[k]).copy() for k in WIDE_KEYS]
+        if name != "fused":
+            res[name + ":dense"] = [to_bits(sv["y1"]).copy(), to_bits(sv["dy2"]).copy()]
+        assert ("y1" in sv) == (name != "fused") and ("y1_kept" in sv) == (name != "unfused")
+    for other in ("fused+dense", "unfused"):
+        for n, (a, b) in enumerate(zip(res["fused"], res[other])):
+            assert np.array_equal(a, b), (other, n)
+    for a, b in zip(res["fused+dense:dense"], res["unfused:dense"]):
+        assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("M", [16, 64])
+def test_grouped_step_wide_blocks(M):
+    """The mixture-of-experts form with blocks of 16 / 64 columns (uneven segments, one of them empty): every expert's share
+    teacher-forced against the oracle like the plain wide-block step."""
+    D, F = 192, 1024
+    m = make_moe_inputs(n_tokens=700, n_experts=3, top_k=2, D=D, F=F, seed=5, zero_fraction=0.75)
+    seg = np.concatenate([m["seg"][:2], m["seg"][1:]]).astype(np.int64)          # an empty segment in second place
+    extra = make_ffn_inputs(64, D, F, seed=99)
+    W1 = np.concatenate([m["W1"][:1], extra["W1"][None], m["W1"][1:]])
+    W2 = np.concatenate([m["W2"][:1], extra["W2"][None], m["W2"][1:]])
+    b1 = np.concatenate([m["b1"][:1], extra["b1"][None], m["b1"][1:]])
+    mm = dict(X=m["X"], dY=m["dY"], W1=W1, W2=W2, b1=b1, seg=seg)
+    dev = {k: to_dev(mm[k]) for k in ("X", "W1", "W2", "b1", "dY")}
+    step = sffn.FfnStepGrouped(seg, D, F, sffn.MODE_HARD, keep_dense=True, M=M)
+    Y3, dX, dW1, dW2 = step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    torch.cuda.synchronize()
+    s = {k: to_bits(v).copy() for k, v in step.saved().items()}
+    outs = dict(Y3=to_bits(Y3), dX=to_bits(dX), dW1=to_bits(dW1), dW2=to_bits(dW2))
+    assert not outs["dW1"][1].any() and not outs["dW2"][1].any()
+    for e in (0, 2, 3):
+        a, b = int(seg[e]), int(seg[e + 1])
+        inp = dict(X=mm["X"][a:b], W1=W1[e], W2=W2[e], b1=b1[e], dY=mm["dY"][a:b])
+        se = {k: s[k][e] for k in ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta")}
+        se.update({k: s[k][a:b] for k in ("y1", "y2_vals", "y2_meta", "dy2", "dy1_vals")})
+        se["colidx"] = s["colidx"][a // 64:b // 64]
+        se["y1_kept"] = s["y1_kept"].reshape(-1)[a * 2 * F // M:b * 2 * F // M]
+        oe = dict(Y3=outs["Y3"][a:b], dX=outs["dX"][a:b], dW1=outs["dW1"][e], dW2=outs["dW2"][e])
+        _check_wide_step_against_oracle(inp, se, oe, sffn.MODE_HARD, M)
 
 
 # ---- neuron-level router (Section 3.3, Alg. 3) -------------------------------------------------------------------
