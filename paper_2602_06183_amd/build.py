@@ -35,6 +35,32 @@ def build(verbose=False, extra_flags=()):
     return LIB
 
 
+def build_host_sanitized(driver_cpp, exe):
+    """The library's sources plus a host-side driver as one executable whose HOST code runs under AddressSanitizer and
+    UndefinedBehaviorSanitizer (device code is compiled as usual and never launched by the driver).  Returns the executable."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=undefined", "-g"]
+    outdir = os.path.join(HERE, "_build", "san")
+    os.makedirs(outdir, exist_ok=True)
+    procs, objs = [], []
+    for src in SOURCES + [driver_cpp]:
+        path = src if os.path.isabs(src) else os.path.join(CSRC, src)
+        obj = os.path.join(outdir, os.path.basename(path).rsplit(".", 1)[0] + ".o")
+        objs.append(obj)
+        flags = FLAGS if path.endswith(".hip") else ["-O1", "-std=c++17", "-fPIC"]
+        cmd = [hipcc, *flags, *san, "-c", path, "-o", obj]
+        procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    for cmd, p in procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            raise RuntimeError("hipcc failed: %s\n%s" % (" ".join(cmd), out))
+    cmd = [hipcc, "--offload-arch=gfx950", "-fsanitize=address,undefined", "-fno-gpu-sanitize", "-o", exe, *objs]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed: %s\n%s" % (" ".join(cmd), r.stdout))
+    return exe
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
     sys.exit(0)

@@ -211,6 +211,18 @@ def test_binding_rejects_mismatched_tensors_before_any_call(monkeypatch):
         step(**good)
 
 
+def test_host_validation_under_sanitizers(tmp_path):
+    """The argument checks of every entry-point family, run from a C++ driver with the library's host code built under
+    AddressSanitizer + UndefinedBehaviorSanitizer: every bad call must come back with its error code and no sanitizer report."""
+    import subprocess
+    from paper_2602_06183_amd import build
+    exe = build.build_host_sanitized(os.path.join(ROOT, "tests", "abi_host_check.cpp"), str(tmp_path / "abi_host_check"))
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env, timeout=120)
+    assert r.returncode == 0, r.stdout
+    assert "all argument checks behave" in r.stdout and "ERROR: AddressSanitizer" not in r.stdout and "runtime error" not in r.stdout, r.stdout
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB", None)
     monkeypatch.setattr(binding, "_HERE", str(tmp_path))
