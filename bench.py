@@ -282,7 +282,7 @@ def main():
         # a narrower layer of the same d_model: the first Fs hidden units (whole V:N:M column blocks; hidden units only meet in
         # the sums of Y3 and dX) on the first Ts tokens, sized for roughly 10-30 s of numpy work
         Fs = F if F * D <= (1 << 25) else max(512, ((1 << 25) // D) // 64 * 64)
-        Ts = min(T, max(64, (int(2.0e11 / (12.0 * D * Fs)) // 64) * 64))
+        Ts = min(T, max(64, (int(5.0e11 / (12.0 * D * Fs)) // 64) * 64))
         inp = hw.host
         w1o, w2o, b1o = (inp[k][0] if hw.moe else inp[k] for k in ("W1", "W2", "b1"))    # moe: expert 0 on its first tokens
         w1o, w2o, b1o = w1o[:Fs], np.ascontiguousarray(w2o[:, :Fs]), b1o[:Fs]
@@ -297,7 +297,7 @@ def main():
                          % ("ffn_router_step_ref" if args.router else "ffn_sparse_step_ref", Ts, T, Fs, F, " of expert 0" if hw.moe else "", dt)}
 
     # ================= the other configurations, stand-alone kernels, micro-benchmarks =============================
-    configs, kernels, gemm24, venom, router, fp8_bench = None, None, None, None, None, None
+    configs, kernels, gemm24, venom, router, fp8_bench, wide, router_step = None, None, None, None, None, None, None, None
     if not args.headline_only and not args.router and M == 8:
         esteps, ewarm = max(3, min(args.steps, 10)), max(1, min(args.warmup, 2))
         configs = {}
@@ -314,9 +314,22 @@ def main():
                 bf = lambda *shape: torch.empty(shape, dtype=torch.bfloat16, device="cuda")
                 hw.y2, hw.dy2, hw.dy1 = bf(T, F), bf(T, F), bf(T, F)
                 configs[key("70b", zf)] = hw.summary(hw.measure(esteps, ewarm))
+        # Table 5's wider blocks at the headline shape (same tensors): the fused wide-block step, retained L1 mass included
+        wide = {}
+        if hw.name == "70b":
+            host70, hw.y1 = hw.host, None
+            del hw
+            free()
+            for m in (16, 32, 64):
+                w = Workload("70b", 0.90, m, host=host70)
+                wide["64:2:%d" % m] = w.summary(w.measure(esteps, ewarm))
+                del w
+                free()
+            del host70
+        else:
+            del hw
+            free()
         host_1b = None
-        del hw
-        free()
         for name in ("tiny", "1b", "7b", "moe"):
             if key(name, 0.90) in configs:
                 continue
@@ -324,6 +337,16 @@ def main():
             configs[key(name, 0.90)] = w.summary(w.measure(esteps if name != "tiny" else 50, ewarm))
             if name == "1b":
                 host_1b = w.host
+            del w
+            free()
+
+        # the neuron-level router's whole training step (Section 3.3; routing + grouping inside the timed step) at the 1B shape
+        router_step = {}
+        for m in (8, 16, 32, 64):
+            w = Workload("1b", 0.90, m, router=True, host=host_1b)
+            r = w.measure(esteps, ewarm)
+            router_step["64:2:%d" % m] = {"experts": m // 4, "ms_per_step": round(r["ms_sparse"], 4), "dense_ms_per_step": round(r["ms_dense"], 4),
+                                          "speedup_vs_dense": round(r["ms_dense"] / r["ms_sparse"], 4)}
             del w
             free()
 
@@ -436,6 +459,8 @@ def main():
         "stage_ms": {k: round(v, 4) for k, v in acc.items()},
         "retained_l1_fraction": head.get("retained_l1_fraction"), "relu_zero_fraction": head.get("relu_zero_fraction"),
         "configs": configs,
+        "wide_blocks_70b": wide,
+        "router_step_1b": router_step,
         "standalone_kernels": kernels,
         "venom_gemm_microbench": venom,
         "gemm24_microbench": gemm24,
