@@ -248,7 +248,8 @@ def main():
     if M != 8:      # wide blocks: eqs. (3), (7) gather rows, eqs. (5), (8) contract the dense transposed activation with the dense-operand tile kernel
         if "step/to24(y2)" not in acc:
             kos.update({"step/y3": "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>", "step/dX": "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>"})
-        kos.update({"step/dW2": DENSE_GEMM, "step/dW1": DENSE_GEMM})
+        if "step/expand(y2)" in acc:    # the unfused path contracts the dense transposed activation; the fused one the compacted operand
+            kos.update({"step/dW2": DENSE_GEMM, "step/dW1": DENSE_GEMM})
     for name, ms in acc.items():
         by_kernel.setdefault(kos.get(name, name), []).append((name, ms))
     dom_kernel = max(by_kernel, key=lambda k: sum(ms for _, ms in by_kernel[k]))

@@ -661,7 +661,8 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     if (fused_wide(cfg)) {
         // Blocks of M = 16, 32, 64 columns (Table 5), fused like the M = 8 step: eq. (2) + compression in the epilogue of eq. (1), eq. (6)
         // in the epilogue of eq. (4) (the dense y1 / dy2 stay in LDS), eqs. (3), (7) on the kept rows of W2.T / W1 only (the pruning
-        // pass of W2 also writes W2.T), eqs. (5), (8) on the dense transposed activation that the epilogues write.  10 launches.
+        // pass of W2 also writes W2.T), eqs. (5), (8) on the compacted transposed activation that the epilogues write in the M = 8 format
+        // (no group of 8 hidden units keeps more than 4 when a block of M >= 16 keeps 4).  10 launches.
         const int M = cfg->M, logM = M == 16 ? 4 : M == 32 ? 5 : 6;
         GemmGroup g_packed = g, g_rows = g, g_wgrad = g;
         g_packed.role = 1; g_packed.a_stride = F * D / 2; g_packed.m_stride = F * D / 8; g_packed.bias_stride = F;
@@ -670,29 +671,26 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
         const GemmGroup* gp = g.n ? &g_packed : nullptr;
         const GemmGroup* gr = g.n ? &g_rows : nullptr;
         const GemmGroup* gw = g.n ? &g_wgrad : nullptr;
-        uint16_t* xt = xtb;                              // X.T and dY.T [D, T], row-major here
-        uint16_t* dyt = dytb;
         uint16_t* w2t = w1tb;                            // W2.T [F, D] per expert
-        uint16_t* at = atb;                              // dense transposed activation [F, T]
         if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
-        STAGE(launch_transpose(X, T, D, D, xt, 0, xb, s), "step/X.T");
+        STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
         STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, w1v, w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
         {
             VnmEpilogue ep;
-            ep.mode = 5; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = y2v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept; ep.at = at;
+            ep.mode = 5; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = y2v; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept; ep.at = atb;
             STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s, gp), "step/y1+sqrelu_vnm_compress");         // eqs. (1), (2), Section 2.3
         }
         STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, w2v, w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
         STAGE(launch_vnm_spmm_gather(y2v, y2m, cix, w2t, D, T, D, F, M, Y3, D, s, gr), "step/y3");                              // eq. (3)
-        STAGE(launch_transpose(dY, T, D, D, dyt, 0, dyb, s), "step/dY.T");
-        STAGE(launch_gemm_nt(0, at, nullptr, dyt, nullptr, F, D, T, 1, dW2, F, s, gw), "step/dW2");                             // eq. (5)
+        STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
+        STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");                                       // eq. (5)
         {
             VnmEpilogue ep;
-            ep.mode = 6; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept; ep.at = at;
+            ep.mode = 6; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept; ep.at = atb;
             STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, ep, s, gp), "step/dy2+dsqrelu_vnm");         // eqs. (4), (6)
         }
         STAGE(launch_vnm_spmm_gather(dy1v, y2m, cix, W1, D, T, D, F, M, dX, D, s, gr), "step/dX");                              // eq. (7), dense W1 as is
-        STAGE(launch_gemm_nt(0, at, nullptr, xt, nullptr, F, D, T, 0, dW1, D, s, gw), "step/dW1");                              // eq. (8)
+        STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                                        // eq. (8)
         return SFFN_OK;
     }
     if (cfg->M != 8) {

@@ -314,8 +314,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         // through LDS as [j][i] (two halves of 64 i) so that HBM sees 128-byte row segments instead of
         // 16-byte ones; the bias (indexed by i) is added before the single rounding to bf16.
         constexpr int EP = 64 * 2 + 16;
-        // EPI: second tile for the transposed output (32 compact rows; 64 dense rows for the wide-block epilogues)
-        constexpr int WAVE_LDS = (GEN_F || GEN_B) ? (WN + 64) * EP : (EPI != 0) ? (WN + 32) * EP : WN * EP;
+        // EPI: second tile (32 compact rows) for the transposed output
+        constexpr int WAVE_LDS = (EPI != 0) ? (WN + 32) * EP : WN * EP;
         unsigned char* scratch = smem + wave * WAVE_LDS;
         static_assert(8 * WAVE_LDS <= C::NSTAGE * C::STAGE, "epilogue scratch must fit in the main-loop LDS");
         unsigned char* ttile = scratch + WN * EP;
@@ -368,10 +368,9 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             tok_ok[b] ? make_uint2(f2bf2(v0, v1), f2bf2(v2, v3)) : make_uint2(0u, 0u);
                     }
             if (EPI == 1 || EPI == 2 || GEN_F || GEN_B) {
-                constexpr int TROWS = (GEN_F || GEN_B) ? 64 : 32;
 #pragma unroll
-                for (int q = 0; q < (TROWS * EP + 1023) / 1024; ++q)
-                    if ((q * 64 + lane) * 16 < TROWS * EP) *reinterpret_cast<uint4*>(ttile + (q * 64 + lane) * 16) = make_uint4(0, 0, 0, 0);
+                for (int q = 0; q < (32 * EP + 1023) / 1024; ++q)
+                    if ((q * 64 + lane) * 16 < 32 * EP) *reinterpret_cast<uint4*>(ttile + (q * 64 + lane) * 16) = make_uint4(0, 0, 0, 0);
             }
             wave_lds_sync();
             if (EPI == 0 || ep.store_dense) {
@@ -444,12 +443,14 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
             if (GEN_F || GEN_B) {
                 // Blocks of M = 16 / 32 / 64 columns (Table 5): the wave's 64 tokens x 64 hidden units hold NB = 64 / M whole blocks.
                 // Lane = column for the ordered scores and the ranking inside a block; lane = (token, block) for the per-row 2:4 choice,
-                // block = lane % NB in every sweep.  The survivors also go, scattered to their hidden units, into a zeroed [64 units x
-                // 64 tokens] tile that leaves as rows of the dense transposed activation [F, T] (operand of the weight-gradient GEMM).
+                // block = lane % NB in every sweep.  The survivors also go into the compacted transposed tile of the weight-gradient GEMM,
+                // in the SAME format as for M = 8 (4 rows per group of 8 hidden units + one kept-column mask byte per group): a block of
+                // M columns keeps 4, so none of its M / 8 groups keeps more than 4; row = 4 * group + number of kept units below it.
                 constexpr int M = 1 << LOGM, NB = 64 >> LOGM;
                 const int64_t nblkM = F >> LOGM, blk0 = f0 >> LOGM;
                 const int b = lane & (NB - 1);
                 uint32_t cb;                                              // the four kept column offsets of block b
+                unsigned long long bmask;                                 // and the same as a bit mask over the block's M columns
                 if (GEN_F) {
                     float sc = 0.0f;
 #pragma unroll 8
@@ -464,16 +465,23 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                     }
                     const unsigned long long kept = __ballot(rank < 4);
                     unsigned long long bits = (M == 64) ? kept : ((kept >> base) & ((1ull << (M & 63)) - 1ull));
+                    const unsigned long long mine = bits;
                     uint32_t cw = 0;
 #pragma unroll
                     for (int n = 0; n < 4; ++n) {
                         cw |= (uint32_t)__builtin_ctzll(bits) << (8 * n);
                         bits &= bits - 1ull;
                     }
-                    if (valid && c == 0) *reinterpret_cast<uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblkM + blk0 + (lane >> LOGM)) * 4) = cw;
+                    if (valid && c < M / 8) {          // lane c of a block: its column offsets (c = 0) and the mask byte of its group c of 8 hidden units
+                        if (c == 0) *reinterpret_cast<uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblkM + blk0 + (lane >> LOGM)) * 4) = cw;
+                        ep.kmask[(int64_t)(t0 >> 6) * (F >> 3) + (f0 >> 3) + (lane >> LOGM) * (M / 8) + c] = (uint8_t)(mine >> (8 * c));
+                    }
                     cb = (uint32_t)__shfl((int)cw, b << LOGM, 64);
+                    bmask = (unsigned long long)(uint32_t)__shfl((int)(uint32_t)mine, b << LOGM, 64);
+                    if (M == 64) bmask |= (unsigned long long)(uint32_t)__shfl((int)(uint32_t)(mine >> 32), b << LOGM, 64) << 32;
                 } else {
                     cb = valid ? *reinterpret_cast<const uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblkM + blk0 + b) * 4) : 0x03020100u;
+                    bmask = (1ull << (cb & 0xFFu)) | (1ull << ((cb >> 8) & 0xFFu)) | (1ull << ((cb >> 16) & 0xFFu)) | (1ull << (cb >> 24));
                 }
                 const uint32_t q0 = (cb & 0xFFu) * 2, q1 = ((cb >> 8) & 0xFFu) * 2, q2 = ((cb >> 16) & 0xFFu) * 2, q3 = (cb >> 24) * 2;
                 const int r_lane = lane >> (6 - LOGM);                    // token of sweep 0; sweep s adds s * M
@@ -527,18 +535,22 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             v = f2bf2(2.0f * d0 * (ya > 0.0f ? ya : 0.0f), 2.0f * d1 * (yb > 0.0f ? yb : 0.0f));
                             vals_p[(int64_t)sw * M * (F >> LOGM)] = v;
                         }
+                        // compact row of a survivor at column o of the block: group (b M + o) / 8 of the half tile, position = kept columns of
+                        // that group below o
                         const uint32_t o0 = (cb >> (8 * (nib & 3u))) & 0xFFu, o1 = (cb >> (8 * (nib >> 2))) & 0xFFu;
-                        *reinterpret_cast<uint16_t*>(ttile + ((b << LOGM) + o0) * EP + t * 2) = (uint16_t)(v & 0xFFFFu);
-                        *reinterpret_cast<uint16_t*>(ttile + ((b << LOGM) + o1) * EP + t * 2) = (uint16_t)(v >> 16);
+                        const uint32_t g0 = (uint32_t)(bmask >> (o0 & ~7u)) & 0xFFu, g1 = (uint32_t)(bmask >> (o1 & ~7u)) & 0xFFu;
+                        const uint32_t r0 = ((b * (M / 8) + (o0 >> 3)) << 2) + __builtin_popcount(g0 & ((1u << (o0 & 7u)) - 1u));
+                        const uint32_t r1 = ((b * (M / 8) + (o1 >> 3)) << 2) + __builtin_popcount(g1 & ((1u << (o1 & 7u)) - 1u));
+                        *reinterpret_cast<uint16_t*>(ttile + r0 * EP + t * 2) = (uint16_t)(v & 0xFFFFu);
+                        *reinterpret_cast<uint16_t*>(ttile + r1 * EP + t * 2) = (uint16_t)(v >> 16);
                     }
                 }
                 wave_lds_sync();
-                if (valid) {
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) {          // 64 hidden units x 64 tokens: rows of 128 bytes of the [F, tokens] matrix
-                        const int fr = q * 8 + (lane >> 3), tc = (lane & 7) * 8;
-                        *reinterpret_cast<uint4*>(ep.at + (int64_t)(f0 + fr) * tok_ld + t0 + tc) = *reinterpret_cast<const uint4*>(ttile + fr * EP + tc * 2);
-                    }
+                for (int q = 0; q < 4; ++q) {          // 2 groups of 16 compact rows x 2 chunks of 32 tokens, 1 KB each
+                    const int fr = (q >> 1) * 16 + (lane >> 2), tc = (q & 1) * 32 + (lane & 3) * 8;
+                    if (valid)
+                        *reinterpret_cast<uint4*>(ep.at + blk_off(f0 / 2 + fr, t0 + tc, tok_ld / 32)) = *reinterpret_cast<const uint4*>(ttile + fr * EP + tc * 2);
                 }
             }
             if (EPI == 1 || EPI == 2) {

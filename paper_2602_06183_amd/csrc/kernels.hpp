@@ -30,8 +30,9 @@ struct VnmEpilogue {
     // mode 4 (the same experts, backward): the tile of dy2c meets (meta, ykept = the stored y1c [rows, F]) and becomes dy1 in y2's
     //        slots: outputs vals (canonical) and v24 (the same, blocked); `out` = dy2c if store_dense.
     // mode 5 / 6 (blocks of M = 2^logM = 16, 32, 64 columns, Table 5): as modes 1 / 2 with outputs vals, meta, colidx (mode 5), ykept
-    //        ([T/64][F/64][64 tokens][64/M blocks] pairs) and `at` = the DENSE transposed activation [F, tokens] row-major; no v24 / m24
-    //        (eqs. (3), (7) gather the kept rows of the dense operand from the canonical arrays).
+    //        ([T/64][F/64][64 tokens][64/M blocks] pairs), `at` + kmask (mode 5) exactly as for modes 1 / 2 (a block of M columns keeps 4, so no
+    //        group of 8 hidden units keeps more than 4); no v24 / m24 (eqs. (3), (7) gather the kept rows of the dense operand from the
+    //        canonical arrays).
     const int32_t* perm = nullptr;
     int logM = 3;
 };
