@@ -118,6 +118,19 @@ int spmm24_fwd(const uint16_t* X, const uint16_t* w_vals, const uint8_t* w_meta,
 int spmm24_dgrad(const uint16_t* dY, const uint16_t* wt_vals, const uint8_t* wt_meta,
                  int64_t T, int64_t N, int64_t K, uint16_t* out, void* stream);
 
+/* The same two contractions on a "prepared" weight operand.  prune24_compress_prepared (rows K-contiguous) writes, next to the
+ * canonical vals / meta, the packed matrix in the layout the matrix-core kernel streams fastest (opaque to the caller:
+ * sffn_prepared24_bytes(R, K) bytes holding 1 KB blocks of 16 rows x 32 values and 256-byte metadata units of 32 rows x 64 k);
+ * spmm24_prepared then computes out[t,n] = bf16( sum_k X[t,k] * Ws[n,k] + bias[n] ) (bias may be NULL: eq. (4)) with the main
+ * loop of the fused step, after one pass that copies X into the same block layout (workspace:
+ * sffn_spmm24_prepared_workspace_bytes(T, K) = 2 T K bytes).  Same sums as spmm24_fwd (fp32 accumulation order may differ). */
+size_t sffn_prepared24_bytes(int64_t R, int64_t K);
+int prune24_compress_prepared(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int mode, uint16_t* vals, uint8_t* meta,
+                              void* prepared, void* stream);
+size_t sffn_spmm24_prepared_workspace_bytes(int64_t T, int64_t K);
+int spmm24_prepared(const uint16_t* X, const void* w_prepared, const float* bias, int64_t T, int64_t N, int64_t K,
+                    uint16_t* out, void* workspace, size_t ws_bytes, void* stream);
+
 /* eq. (3) / Alg. 1 line 7 (w_kmajor=0, Wd = W2 [N,Kfull]) and eq. (7) / Alg. 2 line 5
  * (w_kmajor=1, Wd = W1 [Kfull,N]): out[t,n] = bf16( sum_f Av[t,f] * W(n,f) ) with Av the V:N:M
  * matrix (a_vals [T,Kfull/4], a_meta [T,Kfull/16], a_colidx [T/64,Kfull/8,4]) and W dense.

@@ -59,6 +59,12 @@ def load():
     lib.sqrelu_vnm_compress.argtypes = [p, i64, i64, i32, i32, p, p, p, p]
     lib.spmm24_fwd.argtypes = [p, p, p, p, i64, i64, i64, p, p]
     lib.spmm24_dgrad.argtypes = [p, p, p, i64, i64, i64, p, p]
+    lib.sffn_prepared24_bytes.restype = sz
+    lib.sffn_prepared24_bytes.argtypes = [i64, i64]
+    lib.prune24_compress_prepared.argtypes = [p, i64, i64, i64, i32, p, p, p, p]
+    lib.sffn_spmm24_prepared_workspace_bytes.restype = sz
+    lib.sffn_spmm24_prepared_workspace_bytes.argtypes = [i64, i64]
+    lib.spmm24_prepared.argtypes = [p, p, p, i64, i64, i64, p, p, sz, p]
     lib.vnm_spmm.argtypes = [p, p, p, p, i64, i32, i64, i64, i64, i32, i32, p, p, sz, p]
     lib.dsqrelu_vnm.argtypes = [p, p, p, p, i64, i64, i32, i32, p, p]
     lib.vnm_wgrad.argtypes = [p, p, p, p, i64, i64, i64, i32, i32, i32, p, p, sz, p]
@@ -232,6 +238,33 @@ def spmm24_fwd(X, w_vals, w_meta, bias=None):
     _want("spmm24_fwd: bias", bias, (N,), _F32, optional=True)
     out = _bf16((T, N), X.device)
     _check(load().spmm24_fwd(_ptr(X), _ptr(w_vals), _ptr(w_meta), _ptr(bias), T, N, K, _ptr(out), _stream()))
+    return out
+
+
+def prune24_compress_prepared(src, mode=MODE_HARD):
+    """src [R, K] -> (vals [R, K/2], meta [R, K/8], prepared): the canonical packing plus the same matrix in the layout the
+    matrix-core kernel streams fastest (an opaque byte tensor for spmm24_prepared)."""
+    if src is None or src.dim() != 2 or src.dtype not in _BF16:
+        raise SffnError("prune24_compress_prepared: src must be a 2-D bf16 tensor")
+    R, K = src.shape
+    vals, meta = _bf16((R, K // 2), src.device), _u8((R, K // 8), src.device)
+    prepared = _u8((max(load().sffn_prepared24_bytes(R, K), 16),), src.device)
+    _check(load().prune24_compress_prepared(_ptr(src, True), R, K, src.stride(0), mode, _ptr(vals), _ptr(meta), _ptr(prepared), _stream()))
+    return vals, meta, prepared
+
+
+def spmm24_prepared(X, w_prepared, N, bias=None, workspace=None):
+    """eq. (1) / eq. (4) on a prepared weight operand of N rows: out [T, N]."""
+    if X is None or X.dim() != 2:
+        raise SffnError("spmm24_prepared: X must be a 2-D tensor")
+    T, K = X.shape
+    _want("spmm24_prepared: X", X, (T, K), _BF16)
+    _want("spmm24_prepared: w_prepared", w_prepared, (max(load().sffn_prepared24_bytes(N, K), 16),), _U8)
+    _want("spmm24_prepared: bias", bias, (N,), _F32, optional=True)
+    nbytes = load().sffn_spmm24_prepared_workspace_bytes(T, K)
+    ws = workspace if workspace is not None else _u8((max(nbytes, 16),), X.device)
+    out = _bf16((T, N), X.device)
+    _check(load().spmm24_prepared(_ptr(X), _ptr(w_prepared), _ptr(bias), T, N, K, _ptr(out), _ptr(ws), nbytes, _stream()))
     return out
 
 

@@ -167,6 +167,49 @@ int spmm24_dgrad(const uint16_t* dY, const uint16_t* wt_vals, const uint8_t* wt_
     return spmm24_common("spmm24_dgrad", dY, wt_vals, wt_meta, nullptr, T, N, K, out, stream);
 }
 
+// ---- "prepared" 2:4 operand: the packed matrix in the layout the tile kernel streams fastest (1 KB blocks of values, 256-byte
+//      metadata units), produced by the pruning pass itself, so that the stand-alone GEMMs run the same main loop as the fused step ----
+size_t sffn_prepared24_bytes(int64_t R, int64_t K) {
+    if (!mult64(R) || !mult64(K)) return 0;
+    return up256((size_t)R * K) + up256((size_t)R * K / 8);
+}
+
+int prune24_compress_prepared(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int mode, uint16_t* vals, uint8_t* meta, void* prepared,
+                              void* stream) {
+    REQUIRE(src && vals && meta && prepared, SFFN_EINVAL, "prune24_compress_prepared: null pointer");
+    REQUIRE(mult64(R) && mult64(K), SFFN_EINVAL, "prune24_compress_prepared: R and K must be positive multiples of 64");
+    REQUIRE(ld >= K && ld % 8 == 0, SFFN_EINVAL, "prune24_compress_prepared: ld too small or not a multiple of 8");
+    REQUIRE(mode == SFFN_MODE_HARD || mode == SFFN_MODE_SOFT, SFFN_EINVAL, "prune24_compress_prepared: unknown mode");
+    REQUIRE(aligned16(src) && aligned16(vals) && aligned16(meta) && aligned16(prepared), SFFN_EINVAL, "prune24_compress_prepared: pointers must be 16-byte aligned");
+    REQUIRE(fits_int(R) && fits_int(K) && R / 16 < 65536 * 16, SFFN_EUNSUPPORTED, "prune24_compress_prepared: dimension too large");
+    uint8_t* pb = (uint8_t*)prepared;
+    LAUNCH(launch_prune24_step(src, R, K, ld, 0, mode, vals, meta, (uint16_t*)pb, pb + up256((size_t)R * K), nullptr, (hipStream_t)stream),
+           "prune24_compress_prepared");
+    return SFFN_OK;
+}
+
+size_t sffn_spmm24_prepared_workspace_bytes(int64_t T, int64_t K) {
+    if (!mult64(T) || !mult64(K)) return 0;
+    return up256((size_t)T * K * 2);
+}
+
+int spmm24_prepared(const uint16_t* X, const void* w_prepared, const float* bias, int64_t T, int64_t N, int64_t K, uint16_t* out,
+                    void* workspace, size_t ws_bytes, void* stream) {
+    REQUIRE(X && w_prepared && out, SFFN_EINVAL, "spmm24_prepared: null pointer");
+    REQUIRE(mult64(T) && mult64(N) && mult64(K), SFFN_EINVAL, "spmm24_prepared: T, N, K must be positive multiples of 64");
+    REQUIRE(aligned16(X) && aligned16(w_prepared) && aligned16(out) && aligned16(bias) && aligned16(workspace), SFFN_EINVAL,
+            "spmm24_prepared: pointers must be 16-byte aligned");
+    REQUIRE(fits_int(T) && fits_int(N) && fits_int(K) && T / 64 < 65536, SFFN_EUNSUPPORTED, "spmm24_prepared: dimension too large");
+    REQUIRE(workspace && ws_bytes >= sffn_spmm24_prepared_workspace_bytes(T, K), SFFN_EWORKSPACE, "spmm24_prepared: workspace missing or too small");
+    hipStream_t s = (hipStream_t)stream;
+    uint16_t* xb = (uint16_t*)workspace;
+    const uint8_t* pb = (const uint8_t*)w_prepared;
+    LAUNCH(launch_transpose(X, T, K, K, nullptr, 1, xb, s), "spmm24_prepared/block(X)");         // X once through HBM into 1 KB blocks
+    const VnmEpilogue plain;
+    LAUNCH(launch_gemm_vnm_epilogue((const uint16_t*)pb, pb + up256((size_t)N * K), xb, bias, N, T, K, out, plain, s), "spmm24_prepared/gemm");
+    return SFFN_OK;
+}
+
 int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_colidx, const uint16_t* Wd, int64_t ldw,
              int w_kmajor, int64_t T, int64_t N, int64_t Kfull, int V, int M, uint16_t* out, void* workspace,
              size_t ws_bytes, void* stream) {

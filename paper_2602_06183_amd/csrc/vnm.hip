@@ -101,7 +101,7 @@ __global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* __r
     {   // batched form: matrix blockIdx.z of a stack of [R, C] matrices (map_logM: all read the one source, see the launcher)
         const int64_t m = (int64_t)blockIdx.z * R * C;
         if (!map_logM) in += m;
-        out += m;
+        if (out) out += m;
         if (out_same) out_same += m;
     }
 #pragma unroll
@@ -122,11 +122,13 @@ __global__ void __launch_bounds__(256) transpose_bf16_kernel(const uint16_t* __r
         int cc, rs;                          // output row (a column of `in`) and first of 8 source rows
         if (blocked) { const int bk = e >> 6, l = e & 63; cc = (bk >> 1) * 16 + (l >> 2); rs = (bk & 1) * 32 + (l & 3) * 8; }
         else { cc = e >> 3; rs = (e & 7) * 8; }
-        uint32_t o[4];
+        if (out) {                           // (out = nullptr: only the blocked copy of `in` is wanted)
+            uint32_t o[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] = tile[rs + 2 * j][cc] | ((uint32_t)tile[rs + 2 * j + 1][cc] << 16);
-        uint16_t* dst = blocked ? out + blk_off(c0 + cc, r0 + rs, R / 32) : out + (c0 + cc) * R + r0 + rs;
-        *reinterpret_cast<uint4*>(dst) = make_uint4(o[0], o[1], o[2], o[3]);
+            for (int j = 0; j < 4; ++j) o[j] = tile[rs + 2 * j][cc] | ((uint32_t)tile[rs + 2 * j + 1][cc] << 16);
+            uint16_t* dst = blocked ? out + blk_off(c0 + cc, r0 + rs, R / 32) : out + (c0 + cc) * R + r0 + rs;
+            *reinterpret_cast<uint4*>(dst) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
         if (out_same) {
             const int bk = e >> 6, l = e & 63, rr = (bk >> 1) * 16 + (l >> 2), cs = (bk & 1) * 32 + (l & 3) * 8;
             const uint32_t* p = reinterpret_cast<const uint32_t*>(&tile[rr][cs]);

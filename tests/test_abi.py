@@ -55,6 +55,9 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     assert lib.sqrelu_vnm_compress(fake, 64, 64, 64, 64, fake, fake, fake, None) == -1      # F must be a multiple of 2 M
     assert lib.sqrelu_vnm_compress(fake, 63, 64, 64, 8, fake, fake, fake, None) == -1
     assert lib.spmm24_fwd(fake, fake, fake, None, 64, 64, 65, fake, None) == -1
+    assert lib.sffn_prepared24_bytes(64, 64) == 64 * 64 + 512 and lib.sffn_prepared24_bytes(64, 65) == 0
+    assert lib.prune24_compress_prepared(fake, 64, 64, 32, 0, fake, fake, fake, None) == -1        # ld < K
+    assert lib.spmm24_prepared(fake, fake, None, 64, 64, 64, fake, None, 0, None) == -3            # no workspace
     assert lib.spmm24_dgrad(fake, fake, None, 64, 64, 64, fake, None) == -1
     assert lib.vnm_spmm(fake, fake, fake, fake, 64, 0, 64, 64, 64, 64, 8, fake, None, 0, None) == -3
     assert lib.vnm_spmm(fake, fake, fake, fake, 64, 0, 64, 64, 64, 32, 8, fake, fake, 1 << 20, None) == -2

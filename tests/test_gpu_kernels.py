@@ -116,6 +116,28 @@ def test_spmm24_fwd_and_dgrad(T, N, K):
     assert_gemm_close(to_bits(sffn.spmm24_dgrad(dX, dwv, dwm)), oracle.spmm24(X, wv, wm, None), "dgrad")
 
 
+@pytest.mark.parametrize("mode", [sffn.MODE_HARD, sffn.MODE_SOFT])
+@pytest.mark.parametrize("T,N,K", [(64, 64, 64), (192, 320, 448), (512, 1024, 256), (384, 256, 2048)])
+def test_spmm24_prepared(T, N, K, mode):
+    """The prepared-operand form of eqs. (1), (4): canonical packing bit-exact as prune24_compress, the contraction against the
+    oracle, and exactly on small integers (pins the block / metadata-unit layout)."""
+    rng = np.random.default_rng(T + 3 * N + 7 * K + mode)
+    X = rnd_bits(rng, (T, K))
+    W = rnd_bits(rng, (N, K), 0.02)
+    bias = rng.standard_normal(N).astype(np.float32)
+    vals, meta, prep = sffn.prune24_compress_prepared(to_dev(W), mode)
+    rv, rm = oracle.prune24_compress(W, mode)
+    assert np.array_equal(to_bits(vals), rv) and np.array_equal(to_bits(meta), rm)
+    assert_gemm_close(to_bits(sffn.spmm24_prepared(to_dev(X), prep, N, to_dev(bias))), oracle.spmm24(X, rv, rm, bias), "prepared fwd+bias")
+    assert_gemm_close(to_bits(sffn.spmm24_prepared(to_dev(X), prep, N)), oracle.spmm24(X, rv, rm, None), "prepared dgrad")
+    Xi = bf16_bits_from_f32(rng.integers(-3, 4, (T, K)).astype(np.float32))
+    Wi = bf16_bits_from_f32(rng.integers(-3, 4, (N, K)).astype(np.float32))
+    _, _, pi = sffn.prune24_compress_prepared(to_dev(Wi))
+    iv, im = oracle.prune24_compress(Wi)
+    got = to_bits(sffn.spmm24_prepared(to_dev(Xi), pi, N))
+    assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.spmm24(Xi, iv, im, None)))
+
+
 @pytest.mark.parametrize("T,F,D", [(64, 64, 64), (192, 448, 320), (512, 1024, 256), (256, 2048, 192)])
 def test_vnm_spmm_and_wgrad(T, F, D):
     rng = np.random.default_rng(T + 3 * F + 7 * D)
