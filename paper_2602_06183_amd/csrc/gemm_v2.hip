@@ -19,11 +19,17 @@ namespace {
 // the bf16 kernel (a stage is 128 k instead of 64: 64 survivor bytes per A row, 128 bytes per B row, and the fragment a lane of
 // v_smfmac_f32_32x32x64_fp8_fp8 wants is the same 16 / 2 x 16 bytes), so the kernel runs with K counted in byte pairs and only
 // the metadata differs: 16 survivors per lane and step need a whole 32-bit index word, 16 bytes per row and stage.
+// Measurement switches (never set in the shipped build; results are wrong with the last two): -DSFFN_SPARSE_NSTAGE=2 shortens the
+// structured-sparse kernel's ring, -DSFFN_LOOP_NO_MFMA drops the matrix instructions of its blocked main loop (operand delivery alone),
+// -DSFFN_LOOP_NO_DMA drops the loads after the prologue (matrix pipe, fragment reads and barriers alone).
+#ifndef SFFN_SPARSE_NSTAGE
+#define SFFN_SPARSE_NSTAGE 3
+#endif
 template <bool SPARSE, bool FP8 = false>
 struct Cfg {
     static constexpr int BM = 256, BN = 256;
     static constexpr int BK = SPARSE ? 64 : 32;
-    static constexpr int NSTAGE = SPARSE ? 3 : 4;
+    static constexpr int NSTAGE = SPARSE ? SFFN_SPARSE_NSTAGE : 4;
     static constexpr int A_ROW = 64;                        // bytes per A row per stage (32 survivors or 32 dense k)
     static constexpr int B_ROW = SPARSE ? 128 : 64;
     static constexpr int META_ROW = FP8 ? 16 : 8;
@@ -55,7 +61,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     constexpr bool blocked = BLOCKED;       // operands in the blocked layout of common.hpp (fused step) or row-major (stand-alone entry points)
     using C = Cfg<SPARSE, FP8>;
     constexpr int BM = C::BM, BN = C::BN, WM = 128, WN = 64, FM = 4, FN = 2;
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[C::NSTAGE * C::STAGE];
+    constexpr int EPI_LDS = (EPI != 0) ? 8 * (64 + 32) * (64 * 2 + 16) : 0;        // the epilogues' scratch (see below) when the ring is shorter
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[C::NSTAGE * C::STAGE > EPI_LDS ? C::NSTAGE * C::STAGE : EPI_LDS];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: everything derived from it stays in SGPRs
@@ -168,6 +175,9 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     }
     // the DMA loads of one stage, issued in two halves (h = 0, 1) so that they can sit between matrix instructions
     auto issue_half = [&](int kt, int stage, int h) {
+#ifdef SFFN_LOOP_NO_DMA
+        if (SPARSE && BLOCKED && kt >= C::NSTAGE) return;
+#endif
         unsigned char* sa = smem + stage * C::STAGE;
         unsigned char* sb = sa + C::A_BYTES;
         unsigned char* sm = sb + C::B_BYTES;
@@ -253,6 +263,9 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     };
     // second = the set holds the second 32-k step of its tile: blocked metadata then sits in the high half of the index word
     auto mma_row = [&](const FragSet& f, int a, bool second) {
+#ifdef SFFN_LOOP_NO_MFMA
+        if (SPARSE && BLOCKED) { acc[a][0][0] += __builtin_bit_cast(float, f.a[a].u.x) + __builtin_bit_cast(float, f.b16[a & 1].u[0].x); return; }
+#endif
 #pragma unroll
         for (int b = 0; b < FN; ++b) {
             if (FP8)                    acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x64_fp8_fp8(f.a[a].q, f.b16[b].q, acc[a][b], f.idx[a], 0, 0);
@@ -317,7 +330,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         // EPI: second tile (32 compact rows) for the transposed output
         constexpr int WAVE_LDS = (EPI != 0) ? (WN + 32) * EP : WN * EP;
         unsigned char* scratch = smem + wave * WAVE_LDS;
-        static_assert(8 * WAVE_LDS <= C::NSTAGE * C::STAGE, "epilogue scratch must fit in the main-loop LDS");
+        static_assert(8 * WAVE_LDS <= sizeof(smem), "epilogue scratch must fit in the main-loop LDS");
         unsigned char* ttile = scratch + WN * EP;
         // EPI: i = hidden unit f, j = token t; the wave's 64 tokens are exactly one V = 64 block and each half of
         // 64 f holds 8 whole column blocks, so the V:N:M work is wave-local.
