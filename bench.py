@@ -188,6 +188,17 @@ def main():
             r["ms_sparse2"], r["ms_dense2"] = timed(self.sparse_step, steps), timed(self.dense_step, steps)  # second, interleaved pass: clock drift check
             return r
 
+        def graph_replay_ms(self, steps):
+            """The sparse step captured once in a HIP graph and replayed: what a training loop that captures its iteration pays
+            (the entry points only enqueue kernels on the caller's stream, so they can be captured as they are)."""
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                self.sparse_step()
+            graph.replay()
+            return timed(graph.replay, steps)
+
         def retained_l1(self):
             """How much of the activation's L1 mass the V:N:M format keeps (sum of kept y2 / sum of all y2) and the ReLU zero
             fraction: one extra, untimed step that also stores the dense y1; plain torch reductions, measurement only."""
@@ -336,6 +347,8 @@ def main():
                 continue
             w = Workload(name, 0.90)
             configs[key(name, 0.90)] = w.summary(w.measure(esteps if name != "tiny" else 50, ewarm))
+            if name in ("tiny", "1b"):       # launch gaps are visible at these sizes: the same step replayed from a HIP graph
+                configs[key(name, 0.90)]["graph_replay_ms_per_step"] = round(w.graph_replay_ms(50 if name == "tiny" else esteps), 4)
             if name == "1b":
                 host_1b = w.host
             del w
