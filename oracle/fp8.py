@@ -20,7 +20,8 @@ gives that one statement and no recipe, so everything below is a stated reading:
 import numpy as np
 from .bf16 import bits_to_f32, f64_to_bits
 from .sparse24 import prune24_positions, prune24_decompress, HARD, SOFT
-from .vnm import sqrelu, vnm_select_columns, vnm_decompress, _gather
+from .vnm import sqrelu, vnm_select_columns, vnm_decompress, _gather, sqrelu_vnm_compress, dsqrelu_vnm
+from .gemm import vnm_wgrad
 
 E4M3_MAX = 448.0
 
@@ -151,3 +152,37 @@ def vnm_spmm_fp8(a_codes, a_meta, a_colidx, scale_a, wq, scale_w, w_kmajor, V=64
     if w_kmajor:
         w = w.T
     return _finish(bits_to_f32(a).astype(np.float64) @ w.T, scale_a, scale_w, None)
+
+
+def ffn_sparse_step_fp8_ref(X, W1, W2, b1, dY, scales, mode=HARD, V=64, M=8):
+    """Alg. 1 + Alg. 2 with fp8 operands in the four contractions whose sparse operand is 2:4 along the contraction
+    (eqs. (1), (3), (4), (7)); a stated reading built from the functions above, in the paper's order.
+
+    scales: dict of six per-tensor float32 scales given by the caller (delayed scaling):
+      x, w1, w2, y2, dy, dy1.  Both uses of a weight share its scale (W1: pruned in eq. (1), dense in eq. (7); W2: dense
+      in eq. (3), pruned transposed in eq. (4)).
+    Everything that decides a position stays bf16: y1 is the bf16 output of eq. (1), y2 = bf16(max(y1, 0)^2) picks the
+    columns and the per-row survivors, eq. (6) is evaluated in bf16 arithmetic on the bf16 dy2 and y1 exactly as in the
+    bf16 step, and only then are the survivors quantised for the next contraction.  The weight gradients (eqs. (5), (8),
+    contraction over tokens) stay bf16 on the bf16 survivors and the bf16 dY / X."""
+    s = {k: np.float32(v) for k, v in scales.items()}
+    xq = quantize_fp8(X, s["x"])
+    w1_codes, w1_meta = prune24_compress_fp8(W1, s["w1"], mode)
+    y1 = spmm24_fp8(xq, s["x"], w1_codes, w1_meta, s["w1"], b1)                       # Alg. 1 line 4
+    y2_codes, y2_meta, colidx = sqrelu_vnm_compress_fp8(y1, s["y2"], V, M)           # Alg. 1 lines 5-6
+    y2_vals, meta_b, colidx_b = sqrelu_vnm_compress(y1, V, M)                         # the bf16 survivors (weight gradients)
+    assert np.array_equal(meta_b, y2_meta) and np.array_equal(colidx_b, colidx)
+    w2q = quantize_fp8(W2, s["w2"])
+    y3 = vnm_spmm_fp8(y2_codes, y2_meta, colidx, s["y2"], w2q, s["w2"], 0, V, M)      # Alg. 1 line 7
+    dyq = quantize_fp8(dY, s["dy"])
+    w2t_codes, w2t_meta = prune24_compress_fp8(np.ascontiguousarray(np.asarray(W2).T), s["w2"], mode)
+    dy2 = spmm24_fp8(dyq, s["dy"], w2t_codes, w2t_meta, s["w2"], None)                # Alg. 2 line 2
+    dW2 = vnm_wgrad(y2_vals, y2_meta, colidx, dY, 0, V, M)                            # Alg. 2 line 3 (bf16)
+    dy1_vals = dsqrelu_vnm(dy2, y1, y2_meta, colidx, V, M)                            # Alg. 2 line 4 (bf16 arithmetic)
+    dy1_codes = quantize_fp8(dy1_vals, s["dy1"])
+    w1q = quantize_fp8(W1, s["w1"])
+    dX = vnm_spmm_fp8(dy1_codes, y2_meta, colidx, s["dy1"], w1q, s["w1"], 1, V, M)    # Alg. 2 line 5
+    dW1 = vnm_wgrad(dy1_vals, y2_meta, colidx, X, 1, V, M)                            # Alg. 2 line 6 (bf16)
+    return dict(xq=xq, w1_codes=w1_codes, w1_meta=w1_meta, y1=y1, y2_codes=y2_codes, y2_vals=y2_vals, y2_meta=y2_meta, colidx=colidx,
+                w2q=w2q, y3=y3, dyq=dyq, w2t_codes=w2t_codes, w2t_meta=w2t_meta, dy2=dy2, dW2=dW2, dy1_vals=dy1_vals,
+                dy1_codes=dy1_codes, w1q=w1q, dX=dX, dW1=dW1)

@@ -158,3 +158,89 @@ def test_fp8_contractions_exact_rationals_and_reduction_to_the_bf16_oracle():
     av, _, _ = oracle.sqrelu_vnm_compress(y1)
     for kmaj, wmat in ((0, wq), (1, np.ascontiguousarray(wq.T))):
         assert np.array_equal(fp8.vnm_spmm_fp8(ac, am, aidx, 1.0, fp8.quantize_fp8(wmat, 1.0), 1.0, kmaj), oracle.vnm_spmm(av, am, aidx, wmat, kmaj))
+
+
+# ---- the whole step with fp8 operands (a stated reading: Section 3.4's closing paragraph applied to Alg. 1 / Alg. 2) ----------
+def _step_inputs(T=64, D=32, F=64, seed=0):
+    from workload import make_ffn_inputs
+    return make_ffn_inputs(T, D, F, seed=seed)
+
+
+def _amax(bits):
+    return float(np.max(np.abs(oracle.bits_to_f32(bits))))
+
+
+def _scales_for(inp, ref):
+    """Per-tensor scales of a delayed-scaling recipe: amax / 448 of each quantised tensor, taken from the bf16 step."""
+    y2 = oracle.sqrelu(ref["y1"])
+    return dict(x=_amax(inp["X"]) / 448, w1=_amax(inp["W1"]) / 448, w2=_amax(inp["W2"]) / 448, y2=max(_amax(y2), 1e-6) / 448,
+                dy=_amax(inp["dY"]) / 448, dy1=max(_amax(ref["dy1_vals"]), 1e-6) / 448)
+
+
+def test_fp8_step_stays_within_the_quantisation_error_of_the_bf16_step():
+    """Each fp8 operand carries a relative rounding error of at most 2^-4 (3 mantissa bits), so every contraction of the fp8 step
+    must be close to the bf16 step's - and not equal to it."""
+    inp = _step_inputs(128, 64, 128)
+    ref = oracle.ffn_sparse_step_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"])
+    got = oracle.ffn_sparse_step_fp8_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"], _scales_for(inp, ref))
+    a, b = oracle.bits_to_f32(got["y1"]).astype(np.float64), oracle.bits_to_f32(ref["y1"]).astype(np.float64)
+    rel = np.linalg.norm(a - b) / np.linalg.norm(b)
+    assert 1e-4 < rel < 0.06, rel                     # two operands with <= 2^-4 relative error each, averaged over 32 / 2 products
+
+
+def test_fp8_step_is_invariant_to_power_of_two_changes_of_any_single_scale():
+    """code(x / (s / 2)) decodes to exactly twice code(x / s) while both stay normal numbers below 448, so halving ONE scale must
+    leave every output bit-identical.  Using a tensor's scale on the wrong operand, or forgetting it in the product of the two
+    scales after a contraction, breaks this for that scale.  Small-integer inputs keep every quantised tensor's dynamic range
+    (largest / smallest non-zero magnitude) far below the 2^14 that the normal range of E4M3 spans."""
+    rng = np.random.default_rng(11)
+    T, D, F = 64, 32, 64
+    ints = lambda shape: bf(rng.integers(-2, 3, shape).astype(np.float32))
+    X, W1, W2, dY = ints((T, D)), ints((F, D)), ints((D, F)), ints((T, D))
+    b1 = np.full(F, -2.0, dtype=np.float32)
+    ref = oracle.ffn_sparse_step_ref(X, W1, W2, b1, dY)
+    pow2 = lambda amax: float(2.0 ** np.ceil(np.log2(max(amax, 1.0) / 200.0)))       # largest code magnitude in (100, 200]
+    base = dict(x=pow2(2), w1=pow2(2), w2=pow2(2), dy=pow2(2), y2=pow2(_amax(oracle.sqrelu(ref["y1"]))), dy1=pow2(_amax(ref["dy1_vals"])))
+    want = oracle.ffn_sparse_step_fp8_ref(X, W1, W2, b1, dY, base)
+    for name in ("xq", "w1_codes", "y2_codes", "dyq", "dy1_codes", "w2q", "w1q", "w2t_codes"):
+        mag = np.abs(fp8.e4m3_decode(want[name]))
+        assert mag.max() <= 224 and mag[mag > 0].min() >= 2.0 ** -6, name            # the premise: normal numbers, room to double
+    assert np.count_nonzero(want["y2_codes"]) > 100 and np.count_nonzero(want["dy1_codes"]) > 100
+    for k in base:
+        s2 = dict(base)
+        s2[k] = base[k] * 0.5
+        got = oracle.ffn_sparse_step_fp8_ref(X, W1, W2, b1, dY, s2)
+        for name in ("y1", "y3", "dy2", "dX", "dW1", "dW2", "dy1_vals", "y2_meta", "colidx"):
+            assert np.array_equal(got[name], want[name]), (k, name)
+    # and a scale used on the wrong tensor would show: the codes of the tensor whose scale changed double, the others do not move
+    got = oracle.ffn_sparse_step_fp8_ref(X, W1, W2, b1, dY, dict(base, y2=base["y2"] * 0.5))
+    assert np.array_equal(fp8.e4m3_decode(got["y2_codes"]), 2 * fp8.e4m3_decode(want["y2_codes"])) and np.array_equal(got["dy1_codes"], want["dy1_codes"])
+
+
+def test_fp8_step_positions_are_those_of_the_bf16_rules_on_its_own_y1():
+    """Selection looks at bf16 values only: on the fp8 step's own y1 the bf16 compressor gives the same metadata, column indices
+    and survivors, and the survivors' codes are their quantisation; eq. (6) is the bf16 rule; weight gradients are the bf16 ones."""
+    inp = _step_inputs(64, 32, 64, seed=5)
+    ref = oracle.ffn_sparse_step_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"])
+    sc = _scales_for(inp, ref)
+    got = oracle.ffn_sparse_step_fp8_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"], sc)
+    vals, meta, colidx = oracle.sqrelu_vnm_compress(got["y1"])
+    assert np.array_equal(meta, got["y2_meta"]) and np.array_equal(colidx, got["colidx"]) and np.array_equal(vals, got["y2_vals"])
+    assert np.array_equal(got["y2_codes"], fp8.quantize_fp8(vals, sc["y2"]))
+    assert np.array_equal(got["dy1_vals"], oracle.dsqrelu_vnm(got["dy2"], got["y1"], meta, colidx))
+    assert np.array_equal(got["dW2"], oracle.vnm_wgrad(vals, meta, colidx, inp["dY"], 0))
+    assert np.array_equal(got["dW1"], oracle.vnm_wgrad(got["dy1_vals"], meta, colidx, inp["X"], 1))
+    # weights: the pruned positions are those of the bf16 pruning
+    _, m1 = oracle.prune24_compress(inp["W1"])
+    assert np.array_equal(m1, got["w1_meta"])
+
+
+def test_fp8_step_saturates_instead_of_overflowing():
+    inp = _step_inputs(64, 32, 64, seed=7)
+    ref = oracle.ffn_sparse_step_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"])
+    sc = _scales_for(inp, ref)
+    sc["x"] = sc["x"] / 64                         # X / scale reaches 64 x 448: every large entry clamps to +-448
+    got = oracle.ffn_sparse_step_fp8_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"], sc)
+    dec = fp8.e4m3_decode(got["xq"])
+    assert np.all(np.isfinite(dec)) and np.max(np.abs(dec)) == 448.0 and np.mean(np.abs(dec) == 448.0) > 0.5
+    assert np.all(np.isfinite(oracle.bits_to_f32(got["y3"])))
