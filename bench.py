@@ -309,12 +309,33 @@ def main():
                          % ("ffn_router_step_ref" if args.router else "ffn_sparse_step_ref", Ts, T, Fs, F, " of expert 0" if hw.moe else "", dt)}
 
     # ================= the other configurations, stand-alone kernels, micro-benchmarks =============================
-    configs, kernels, gemm24, venom, router, fp8_bench, wide, router_step = None, None, None, None, None, None, None, None
+    configs, kernels, gemm24, venom, router, fp8_bench, wide, router_step, fp8_step = None, None, None, None, None, None, None, None, None
     if not args.headline_only and not args.router and M == 8:
         esteps, ewarm = max(3, min(args.steps, 10)), max(1, min(args.warmup, 2))
         configs = {}
         key = lambda name, zf: "%s@%.2f" % (name, zf)
         configs[key(hw.name, hw.zf)] = dict(head, headline=True)
+        # The same step with fp8 (E4M3) operands in eqs. (1), (3), (4), (7) (Section 3.4, closing paragraph), weight gradients in bf16.
+        # Per-tensor scales as a delayed-scaling recipe would hold them: amax / 448 of each quantised tensor, here from the bf16 step just run.
+        if not hw.moe and hw.D % 128 == 0 and hw.F % 128 == 0:
+            sv = hw.step.saved()
+            amax = lambda t: max(float(t.float().abs().max()), 1e-12)
+            sc = dict(x=amax(hw.X) / 448, w1=amax(hw.W1) / 448, w2=amax(hw.W2) / 448, y2=amax(sv["y2_vals"]) / 448, dy=amax(hw.dY) / 448,
+                      dy1=amax(sv["dy1_vals"]) / 448)
+            st8 = sffn.FfnStepFp8(hw.T, hw.D, hw.F, sc, mode)
+            run8 = lambda: st8(hw.X, hw.W1, hw.W2, hw.b1, hw.dY)
+            for _ in range(ewarm):
+                run8()
+            ms8 = timed(run8, esteps)
+            ms16 = timed(hw.sparse_step, esteps)
+            msd = timed(hw.dense_step, esteps)
+            tf8 = hw.flops / (ms8 * 1e-3) / 1e12
+            fp8_step = {"workload": hw.name, "ms_per_step": round(ms8, 4), "bf16_sparse_ms_per_step": round(ms16, 4), "dense_bf16_ms_per_step": round(msd, 4),
+                        "speedup_vs_dense_bf16": round(msd / ms8, 4), "speedup_vs_sparse_bf16": round(ms16 / ms8, 4),
+                        "tflops_dense_equiv": round(tf8, 2), "operands": "E4M3 codes in eqs. (1), (3), (4), (7), quantised inside the pruning passes and the "
+                        "V:N:M epilogues; eqs. (5), (8) bf16; six per-tensor scales = amax / 448"}
+            del st8, sv
+            free()
         # configs[3]'s sweep of the ReLU zero fraction: same tensors, only the bias shifts
         if hw.name == "70b":
             std = neuron_std(hw.host["W1"])
@@ -487,6 +508,7 @@ def main():
         "venom_gemm_microbench": venom,
         "gemm24_microbench": gemm24,
         "fp8_microbench": fp8_bench,
+        "fp8_step": fp8_step,
         "router_conversion": router,
         "roofline": roofline, "cpu_baseline": cpu,
         "paper_context": "paper reports 1.4-1.5x for 2:4 GEMMs and 1.4-1.7x end-to-end on NVIDIA sparse tensor cores (Sections 1, 5.2.3); context, not a target",

@@ -172,7 +172,7 @@ int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_co
  *   vnm_spmm_fp8            eqs. (3), (7): the V:N:M code matrix (a_codes [T, 2 Kfull/M]) times dense W codes, [N, Kfull]
  *                           (w_kmajor = 0) or [Kfull, N] (1, contiguous rows); Kfull a multiple of 128, T below 65536;
  *                           workspace: sffn_vnm_spmm_fp8_workspace_bytes()
- * The weight gradients (eqs. (5), (8), contraction over tokens) have no fp8 form here. */
+ * The weight gradients (eqs. (5), (8), contraction over tokens) have no fp8 form here.  ffn_sparse_step_fp8 below is the whole step. */
 int quantize_fp8(const uint16_t* src, int64_t n, float scale, uint8_t* codes, float* amax, void* stream);
 int prune24_compress_fp8(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float scale,
                          uint8_t* codes, uint8_t* meta, float* amax, void* stream);
@@ -184,6 +184,27 @@ size_t sffn_vnm_spmm_fp8_workspace_bytes(int64_t T, int64_t N, int64_t Kfull);
 int vnm_spmm_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* a_colidx, float scale_a, const uint8_t* Wq,
                  float scale_w, int w_kmajor, int64_t T, int64_t N, int64_t Kfull, int V, int M, uint16_t* out,
                  void* workspace, size_t ws_bytes, void* stream);
+
+/* Alg. 1 + Alg. 2 with fp8 operands in the four contractions whose sparse operand is 2:4 along the contraction (eqs. (1), (3),
+ * (4), (7)); the reading of Section 3.4's closing paragraph applied to the whole step.  Six per-tensor scales, given by the caller
+ * (host struct): x, w1, w2, y2, dy, dy1; a weight keeps one scale for both of its uses.  X, dY, the dense W2 (eq. (3)) and the
+ * dense W1 (eq. (7)) are quantised by plain scans, the pruned W1 / W2.T inside the pruning pass, y2's and dy1's survivors inside
+ * the epilogues of eqs. (1) / (4).  Everything that decides a position stays bf16 (y1, y2, the column scores, the 2:4 choices,
+ * eq. (6)), so metadata and column indices are those the bf16 rules give on this step's own y1; the weight gradients (eqs. (5),
+ * (8)) are the bf16 contractions on the bf16 survivors.  out = bf16( (sum dec * dec) * (scale_a * scale_b) [+ b1] ).
+ * Shapes: V = 64, M = 8, T a multiple of 64, D and F multiples of 128; cfg->flags: SFFN_FLAG_KEEP_DENSE or 0.
+ * Workspace: sffn_fp8_workspace_bytes(cfg); after the call it holds, at the offsets of sffn_fp8_workspace_layout: the pruned
+ * weights (codes [F, D/2] u8 + meta [F, D/8]), y2 (codes [T, F/4] u8, meta [T, F/16], colidx [T/64, F/8, 4]), dy1 at y2's slots
+ * (bf16 [T, F/4]), y1 at y2's slots (y1_kept, runs of 64 tokens x 8 blocks as in ffn_sparse_step) and, with KEEP_DENSE, y1 / dy2. */
+typedef struct { float x, w1, w2, y2, dy, dy1; } sffn_fp8_scales;
+typedef struct {
+    size_t w1_codes, w1_meta, w2t_codes, w2t_meta, y1, y2_codes, y2_meta, colidx, dy2, dy1_vals, y1_kept, total;
+} sffn_fp8_ws_layout;
+size_t sffn_fp8_workspace_bytes(const sffn_cfg* cfg);
+int sffn_fp8_workspace_layout(const sffn_cfg* cfg, sffn_fp8_ws_layout* out);
+int ffn_sparse_step_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* scales, const uint16_t* X, const uint16_t* W1,
+                        const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
+                        uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
 
 /* Section 3.3 / Alg. 3 ("Convert Activation to Venom") and the conversion steps 1-3 of Section 3.4: neuron-level
  * experts that produce the V:N:M activation directly.  Reading built here: E = M/4 experts; expert e owns the hidden

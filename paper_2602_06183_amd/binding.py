@@ -27,6 +27,15 @@ class _Layout(ctypes.Structure):
                                                "colidx", "dy2", "dy1_vals", "y1_kept", "y1_kept_bytes", "total")]
 
 
+class _Fp8Layout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_size_t) for n in ("w1_codes", "w1_meta", "w2t_codes", "w2t_meta", "y1", "y2_codes", "y2_meta", "colidx",
+                                               "dy2", "dy1_vals", "y1_kept", "total")]
+
+
+class _Fp8Scales(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_float) for n in ("x", "w1", "w2", "y2", "dy", "dy1")]
+
+
 class _RouterLayout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in ("y1c", "vals", "meta", "colidx", "dy2c", "dvals", "total")]
 
@@ -97,6 +106,10 @@ def load():
     lib.sffn_vnm_spmm_fp8_workspace_bytes.restype = sz
     lib.sffn_vnm_spmm_fp8_workspace_bytes.argtypes = [i64, i64, i64]
     lib.vnm_spmm_fp8.argtypes = [p, p, p, f32, p, f32, i32, i64, i64, i64, i32, i32, p, p, sz, p]
+    lib.sffn_fp8_workspace_bytes.restype = sz
+    lib.sffn_fp8_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg)]
+    lib.sffn_fp8_workspace_layout.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Layout)]
+    lib.ffn_sparse_step_fp8.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Scales), p, p, p, p, p, p, p, p, p, p, sz, p]
     lib.sffn_dense_sqrelu.argtypes = [p, p, i64, p]
     lib.sffn_dense_dsqrelu.argtypes = [p, p, p, i64, p]
     lib.sffn_profile_enable.argtypes = [i32]
@@ -500,6 +513,55 @@ def vnm_spmm_fp8(a_codes, a_meta, a_colidx, scale_a, Wq, scale_w, w_kmajor, V=64
     _check(load().vnm_spmm_fp8(_ptr(a_codes), _ptr(a_meta), _ptr(a_colidx), float(scale_a), _ptr(Wq), float(scale_w), int(w_kmajor), T, N, Kfull,
                                V, M, _ptr(out), _ptr(ws), nbytes, _stream()))
     return out
+
+
+class FfnStepFp8:
+    """ffn_sparse_step_fp8 with outputs and workspace allocated once.  scales: dict with the six per-tensor scales
+    x, w1, w2, y2, dy, dy1 (positive floats; delayed scaling: the caller derives them from earlier steps)."""
+
+    def __init__(self, T, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False):
+        self.T, self.D, self.F, self.mode = T, D, F, mode
+        self.cfg = _cfg(T, D, F, mode, M=8, flags=FLAG_KEEP_DENSE if keep_dense else 0)
+        self.scales = _Fp8Scales(*[float(scales[k]) for k in ("x", "w1", "w2", "y2", "dy", "dy1")])
+        lay = _Fp8Layout()
+        _check(load().sffn_fp8_workspace_layout(ctypes.byref(self.cfg), ctypes.byref(lay)))
+        self.layout = {n: getattr(lay, n) for n, _ in _Fp8Layout._fields_}
+        self.keep_dense = keep_dense
+        self.ws = _u8((self.layout["total"],), device)
+        self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
+        self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
+
+    def __call__(self, X, W1, W2, b1, dY):
+        T, D, F = self.T, self.D, self.F
+        _want("ffn_sparse_step_fp8: X", X, (T, D), _BF16)
+        _want("ffn_sparse_step_fp8: W1", W1, (F, D), _BF16)
+        _want("ffn_sparse_step_fp8: W2", W2, (D, F), _BF16)
+        _want("ffn_sparse_step_fp8: b1", b1, (F,), _F32, optional=True)
+        _want("ffn_sparse_step_fp8: dY", dY, (T, D), _BF16)
+        _check(load().ffn_sparse_step_fp8(ctypes.byref(self.cfg), ctypes.byref(self.scales), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY),
+                                          _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _stream()))
+        return self.Y3, self.dX, self.dW1, self.dW2
+
+    def saved(self):
+        """Views of what the step leaves in its workspace."""
+        T, D, F, L = self.T, self.D, self.F, self.layout
+
+        def view(off, shape, dtype):
+            n = 1
+            for d in shape:
+                n *= d
+            nbytes = n * (2 if dtype == torch.bfloat16 else 1)
+            return self.ws[off:off + nbytes].view(dtype).view(shape)
+
+        u8 = torch.uint8
+        out = dict(w1_codes=view(L["w1_codes"], (F, D // 2), u8), w1_meta=view(L["w1_meta"], (F, D // 8), u8),
+                   w2t_codes=view(L["w2t_codes"], (F, D // 2), u8), w2t_meta=view(L["w2t_meta"], (F, D // 8), u8),
+                   y2_codes=view(L["y2_codes"], (T, F // 4), u8), y2_meta=view(L["y2_meta"], (T, F // 16), u8),
+                   colidx=view(L["colidx"], (T // 64, F // 8, 4), u8), dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16),
+                   y1_kept=view(L["y1_kept"], (T, F // 4), torch.bfloat16))
+        if self.keep_dense:
+            out["y1"], out["dy2"] = view(L["y1"], (T, F), torch.bfloat16), view(L["dy2"], (T, F), torch.bfloat16)
+        return out
 
 
 NOALLOC_WORKSPACE_MAX = 32 << 20

@@ -24,6 +24,14 @@ __device__ __forceinline__ uint32_t f2bf2(float lo, float hi) {      // -> bf16(
 }
 __device__ __forceinline__ uint32_t f2bf(float f) { return f2bf2(f, 0.0f) & 0xFFFFu; }
 
+// two real values -> two OCP E4M3 codes in the low 16 bits (first value in the low byte): one float32 product with inv = 1 / scale,
+// saturation to +-448 (v_cvt_pk_fp8_f32 would give NaN above 464), one round-to-nearest-even
+__device__ __forceinline__ uint32_t fp8_enc2(float a, float b, float inv) {
+    const float ma = __builtin_fminf(__builtin_fmaxf(a * inv, -448.0f), 448.0f);
+    const float mb = __builtin_fminf(__builtin_fmaxf(b * inv, -448.0f), 448.0f);
+    return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(ma, mb, 0, false) & 0xFFFFu;
+}
+
 // 2:4 selection on one group of four bf16 (a0..a3 as 16-bit patterns): rank by magnitude
 // descending, index ascending; the two first survive (Section 2.2 of the paper, with the tie rule
 // of the packed-format contract).  Returns v0 | v1 << 16 (survivors in ascending position) and
@@ -61,6 +69,8 @@ __device__ __forceinline__ uint32_t select24(uint32_t a0, uint32_t a1, uint32_t 
 __host__ __device__ __forceinline__ int64_t blk_off(int64_t r, int64_t k, int64_t KC) {
     return (((r >> 4) * KC + (k >> 5)) << 9) + ((r & 15) << 5) + (k & 31);
 }
+// fp8 operands use the same layout with a pair of 1-byte codes in the place of a 2-byte element (a block = 16 rows x 64 codes):
+// blk_off(r, kbyte / 2, row bytes / 64) indexes 16-bit pairs.
 // Metadata of a 2:4 matrix, blocked for the sparse matrix instruction: one 256-byte unit per (32 rows, 64 k).
 // v_smfmac_f32_32x32x32_bf16 wants, in lane (row % 32) + 32 * h, the sixteen index bits of the row's survivors
 // in k 16h..16h+15 of a 32-k step; a unit stores, for each such lane, the two 32-k steps s = 0, 1 of its 64 k as

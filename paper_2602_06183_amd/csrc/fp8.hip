@@ -8,6 +8,8 @@
 //   sqrelu_vnm_compress_fp8        eq. (2) + Section 2.3 + quantisation: codes [T, 2F/M], metadata, column indices
 //   vnm_to_24_fp8                  the V:2:M code matrix as a plain 2:4 code matrix over all columns (operand of eqs. (3), (7))
 //   transpose_u8                   [R, C] bytes -> [C, R]
+//   quantize_fp8_blocked / transpose_quantize_fp8_blocked / prune24_*_fp8 with codes_blk: operands of the fused fp8 step, in the blocked
+//                                  layout of common.hpp with a pair of codes per 2-byte element
 // Every kernel can record the largest magnitude it quantised (float32, atomic max on the bit pattern) for the caller's next scale.
 #include "common.hpp"
 #include "kernels.hpp"
@@ -16,12 +18,7 @@ namespace sffn {
 
 namespace {
 
-// two real values -> two E4M3 codes in the low 16 bits (first value in the low byte)
-__device__ __forceinline__ uint32_t enc2(float a, float b, float inv) {
-    const float ma = __builtin_fminf(__builtin_fmaxf(a * inv, -448.0f), 448.0f);
-    const float mb = __builtin_fminf(__builtin_fmaxf(b * inv, -448.0f), 448.0f);
-    return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(ma, mb, 0, false) & 0xFFFFu;
-}
+__device__ __forceinline__ uint32_t enc2(float a, float b, float inv) { return fp8_enc2(a, b, inv); }
 
 __device__ __forceinline__ void note_amax(float* amax, float m) {      // m >= 0; one atomic per wavefront
 #pragma unroll
@@ -67,7 +64,8 @@ __global__ void __launch_bounds__(256) quantize_fp8_kernel(const uint4* __restri
 // rows K-contiguous: one thread per 8 consecutive elements (two groups) -> 4 codes + 1 metadata byte
 template <bool SOFT>
 __global__ void __launch_bounds__(256) prune24_rows_fp8_kernel(const uint16_t* __restrict__ src, int64_t nchunks, int cpr, int64_t ld, float inv,
-                                                              uint8_t* __restrict__ codes, uint8_t* __restrict__ meta, float* __restrict__ amax) {
+                                                              uint8_t* __restrict__ codes, uint8_t* __restrict__ meta, float* __restrict__ amax,
+                                                              uint16_t* __restrict__ codes_blk) {
     const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
     float m = 0.0f;
     if (c < nchunks) {
@@ -78,8 +76,10 @@ __global__ void __launch_bounds__(256) prune24_rows_fp8_kernel(const uint16_t* _
         select24_f32<SOFT>(w.x & 0xFFFFu, w.x >> 16, w.y & 0xFFFFu, w.y >> 16, n0, a, b);
         select24_f32<SOFT>(w.z & 0xFFFFu, w.z >> 16, w.w & 0xFFFFu, w.w >> 16, n1, d, e);
         m = __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(a), __builtin_fabsf(b)), __builtin_fmaxf(__builtin_fabsf(d), __builtin_fabsf(e)));
-        *reinterpret_cast<uint32_t*>(codes + c * 4) = enc2(a, b, inv) | (enc2(d, e, inv) << 16);
+        const uint32_t q4 = enc2(a, b, inv) | (enc2(d, e, inv) << 16);
+        *reinterpret_cast<uint32_t*>(codes + c * 4) = q4;
         meta[c] = (uint8_t)(n0 | (n1 << 4));
+        if (codes_blk) *reinterpret_cast<uint32_t*>(codes_blk + blk_off(r, (c - r * cpr) * 2, cpr / 16)) = q4;   // 4 codes = pairs 2 c', 2 c' + 1; K / 2 bytes per row
     }
     note_amax(amax, m);
 }
@@ -87,7 +87,8 @@ __global__ void __launch_bounds__(256) prune24_rows_fp8_kernel(const uint16_t* _
 // groups run along the strided axis: S[r, k] = src[k * ld + r]; a workgroup takes 64 logical rows x 128 k through LDS
 template <bool SOFT>
 __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* __restrict__ src, int64_t R, int K, int64_t ld, float inv,
-                                                              uint8_t* __restrict__ codes, uint8_t* __restrict__ meta, float* __restrict__ amax) {
+                                                              uint8_t* __restrict__ codes, uint8_t* __restrict__ meta, float* __restrict__ amax,
+                                                              uint16_t* __restrict__ codes_blk, uint16_t* __restrict__ src_q_blk) {
     constexpr int TK = 128, TR = 64, PITCH = TR + 8;
     __shared__ __attribute__((aligned(16))) uint16_t tile[TK * PITCH];
     const int64_t r0 = (int64_t)blockIdx.x * TR;
@@ -99,6 +100,10 @@ __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* _
         uint4 w = make_uint4(0, 0, 0, 0);
         if (k0 + kk < K) w = *reinterpret_cast<const uint4*>(src + (int64_t)(k0 + kk) * ld + r0 + seg * 8);
         *reinterpret_cast<uint4*>(&tile[kk * PITCH + seg * 8]) = w;
+        if (src_q_blk && k0 + kk < K)      // the unpruned source itself, quantised, in its own orientation [K rows, R codes] (blocked pairs)
+            *reinterpret_cast<uint2*>(src_q_blk + blk_off(k0 + kk, (r0 + seg * 8) / 2, R / 64)) =
+                make_uint2(enc2(bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), inv) | (enc2(bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16), inv) << 16),
+                           enc2(bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), inv) | (enc2(bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16), inv) << 16));
     }
     __syncthreads();
     const int rr = tid % 64, q = tid / 64;
@@ -119,6 +124,7 @@ __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* _
         const int64_t r = r0 + rr;
         *reinterpret_cast<uint4*>(codes + r * (K / 2) + (k0 + 32 * q) / 2) = make_uint4(oc[0], oc[1], oc[2], oc[3]);
         *reinterpret_cast<uint32_t*>(meta + r * (K / 8) + (k0 + 32 * q) / 8) = mbytes;
+        if (codes_blk) *reinterpret_cast<uint4*>(codes_blk + blk_off(r, (k0 + 32 * q) / 4, K / 128)) = make_uint4(oc[0], oc[1], oc[2], oc[3]);   // 16 codes = 8 pairs
     }
     note_amax(amax, m);
 }
@@ -246,23 +252,89 @@ __global__ void __launch_bounds__(256) transpose_u8_kernel(const uint8_t* __rest
     }
 }
 
+// [R, C] bf16 (row stride ld) -> codes in the blocked pair layout, same orientation: one thread per 8 elements
+__global__ void __launch_bounds__(256) quantize_fp8_blocked_kernel(const uint16_t* __restrict__ src, int64_t R, int C8, int64_t ld, float inv,
+                                                                  uint16_t* __restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= R * C8) return;
+    const int64_t r = i / C8;
+    const int c = (int)(i - r * C8) * 8;
+    const uint4 w = *reinterpret_cast<const uint4*>(src + r * ld + c);
+    *reinterpret_cast<uint2*>(out + blk_off(r, c / 2, C8 / 8)) =
+        make_uint2(enc2(bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), inv) | (enc2(bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16), inv) << 16),
+                   enc2(bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), inv) | (enc2(bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16), inv) << 16));
+}
+
+// [R, C] bf16 -> codes of the transposed matrix [C, R] in the blocked pair layout; 64 x 64 tiles through LDS
+__global__ void __launch_bounds__(256) transpose_quantize_fp8_blocked_kernel(const uint16_t* __restrict__ src, int64_t R, int64_t C, int64_t ld, float inv,
+                                                                            uint16_t* __restrict__ out) {
+    __shared__ uint16_t tile[64][64 + 2];
+    const int tid = threadIdx.x;
+    const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = tid / 8 + 32 * i, seg = tid % 8;
+        const uint4 w = *reinterpret_cast<const uint4*>(src + (r0 + r) * ld + c0 + seg * 8);
+        uint32_t* d = reinterpret_cast<uint32_t*>(&tile[r][seg * 8]);
+        d[0] = w.x; d[1] = w.y; d[2] = w.z; d[3] = w.w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = tid / 8 + 32 * i, rs = (tid % 8) * 8;          // output row c0 + c, its 8 codes for source rows r0 + rs .. + 7
+        uint32_t q[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) q[j] = enc2(bf2f(tile[rs + 2 * j][c]), bf2f(tile[rs + 2 * j + 1][c]), inv);
+        *reinterpret_cast<uint2*>(out + blk_off(c0 + c, (r0 + rs) / 2, R / 64)) = make_uint2(q[0] | (q[1] << 16), q[2] | (q[3] << 16));
+    }
+}
+
+hipError_t launch_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_blk, hipStream_t s) {
+    if (C % 64 != 0 || R % 16 != 0) return hipErrorInvalidValue;
+    const int64_t n = R * (C / 8);
+    hipLaunchKernelGGL(quantize_fp8_blocked_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, R, (int)(C / 8), ld, inv, reinterpret_cast<uint16_t*>(out_blk));
+    return hipGetLastError();
+}
+
+hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s) {
+    if (C % 64 != 0 || R % 64 != 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(transpose_quantize_fp8_blocked_kernel, dim3((unsigned)(C / 64), (unsigned)(R / 64)), dim3(256), 0, s, src, R, C, ld, inv,
+                       reinterpret_cast<uint16_t*>(out_t_blk));
+    return hipGetLastError();
+}
+
 hipError_t launch_quantize_fp8(const uint16_t* src, int64_t n, float inv, uint8_t* codes, float* amax, hipStream_t s) {
     const int64_t n8 = n / 8, blocks = (n8 + 255) / 256;
     hipLaunchKernelGGL(quantize_fp8_kernel, dim3((unsigned)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, s, (const uint4*)src, n8, inv, (uint2*)codes, amax);
     return hipGetLastError();
 }
 
+static hipError_t launch_prune24_fp8_impl(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
+                                          float* amax, uint16_t* blk, uint16_t* srcq, hipStream_t s);
+
 hipError_t launch_prune24_fp8(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
                               float* amax, hipStream_t s) {
+    return launch_prune24_fp8_impl(src, R, K, ld, trans, mode, inv, codes, meta, amax, nullptr, nullptr, s);
+}
+
+hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
+                                   uint8_t* codes_blk, hipStream_t s, uint8_t* src_q_blk) {
+    if (K % 128 != 0 || (src_q_blk && (!trans || R % 64 != 0 || K % 16 != 0))) return hipErrorInvalidValue;   // a block row holds whole 64-byte pieces of the K / 2 codes per row
+    return launch_prune24_fp8_impl(src, R, K, ld, trans, mode, inv, codes, meta, nullptr, reinterpret_cast<uint16_t*>(codes_blk),
+                                   reinterpret_cast<uint16_t*>(src_q_blk), s);
+}
+
+static hipError_t launch_prune24_fp8_impl(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
+                                          float* amax, uint16_t* blk, uint16_t* srcq, hipStream_t s) {
     if (!trans) {
         const int64_t nchunks = R * (K / 8);
         const unsigned grid = (unsigned)((nchunks + 255) / 256);
-        if (mode == 0) hipLaunchKernelGGL((prune24_rows_fp8_kernel<false>), dim3(grid), dim3(256), 0, s, src, nchunks, (int)(K / 8), ld, inv, codes, meta, amax);
-        else           hipLaunchKernelGGL((prune24_rows_fp8_kernel<true>), dim3(grid), dim3(256), 0, s, src, nchunks, (int)(K / 8), ld, inv, codes, meta, amax);
+        if (mode == 0) hipLaunchKernelGGL((prune24_rows_fp8_kernel<false>), dim3(grid), dim3(256), 0, s, src, nchunks, (int)(K / 8), ld, inv, codes, meta, amax, blk);
+        else           hipLaunchKernelGGL((prune24_rows_fp8_kernel<true>), dim3(grid), dim3(256), 0, s, src, nchunks, (int)(K / 8), ld, inv, codes, meta, amax, blk);
     } else {
         dim3 grid((unsigned)(R / 64), (unsigned)((K + 127) / 128));
-        if (mode == 0) hipLaunchKernelGGL((prune24_cols_fp8_kernel<false>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax);
-        else           hipLaunchKernelGGL((prune24_cols_fp8_kernel<true>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax);
+        if (mode == 0) hipLaunchKernelGGL((prune24_cols_fp8_kernel<false>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq);
+        else           hipLaunchKernelGGL((prune24_cols_fp8_kernel<true>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq);
     }
     return hipGetLastError();
 }

@@ -15,7 +15,8 @@ namespace sffn {
 
 namespace {
 
-// FP8 (structured-sparse kernel on row-major operands only): both operands are 1-byte E4M3 codes.  In BYTES the tiles are those of
+// FP8 (structured-sparse kernel): both operands are 1-byte E4M3 codes, row-major (stand-alone entry points) or blocked with a pair
+// of codes per 2-byte element (fused fp8 step); the metadata is row-major [R, K/8] in both cases.  In BYTES the tiles are those of
 // the bf16 kernel (a stage is 128 k instead of 64: 64 survivor bytes per A row, 128 bytes per B row, and the fragment a lane of
 // v_smfmac_f32_32x32x64_fp8_fp8 wants is the same 16 / 2 x 16 bytes), so the kernel runs with K counted in byte pairs and only
 // the metadata differs: 16 survivors per lane and step need a whole 32-bit index word, 16 bytes per row and stage.
@@ -57,7 +58,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     constexpr bool GEN_F = EPI >= 16 && EPI < 32, GEN_B = EPI >= 32;
     constexpr int LOGM = (GEN_F || GEN_B) ? (EPI & 15) : 3;
     static_assert(!(GEN_F || GEN_B) || (LOGM >= 4 && LOGM <= 6), "wide V:N:M blocks: M = 16, 32 or 64");
-    static_assert(!FP8 || (SPARSE && !BLOCKED && EPI == 0), "fp8 operands: structured-sparse kernel on row-major operands");
+    static_assert(!FP8 || (SPARSE && (EPI == 0 || (BLOCKED && (EPI == 1 || EPI == 2)))), "fp8 operands: structured-sparse kernel; fused epilogues for M = 8 only");
     constexpr bool blocked = BLOCKED;       // operands in the blocked layout of common.hpp (fused step) or row-major (stand-alone entry points)
     using C = Cfg<SPARSE, FP8>;
     constexpr int BM = C::BM, BN = C::BN, WM = 128, WN = 64, FM = 4, FN = 2;
@@ -167,11 +168,11 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         if (FP8) m_lane = (uint32_t)((lane >> 2) * (Kld / 4) + (lane & 3) * 4);
         if (SPARSE) {
             int gr = i0 + wave * 32; gr = gr < Ra ? gr : Ra - 32;
-            m_base = uniform64(blocked ? a_meta + ((int64_t)(gr >> 5) * (Kld / 64) << 8) : a_meta + (int64_t)gr * (FP8 ? Kld / 4 : Kld / 8));
+            m_base = uniform64(FP8 ? a_meta + (int64_t)gr * (Kld / 4) : blocked ? a_meta + ((int64_t)(gr >> 5) * (Kld / 64) << 8) : a_meta + (int64_t)gr * (Kld / 8));
         }
         a_kstep = blocked ? 1024 : 64;
         b_kstep = blocked ? 1024 * (C::BK / 32) : C::BK * 2;
-        m_kstep = blocked ? 256 : C::META_ROW;
+        m_kstep = (blocked && !FP8) ? 256 : C::META_ROW;
     }
     // the DMA loads of one stage, issued in two halves (h = 0, 1) so that they can sit between matrix instructions
     auto issue_half = [&](int kt, int stage, int h) {
@@ -208,7 +209,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         const int row = wm * WM + a * 32 + l32;
         a_off[a] = row * 64 + ((lh ^ ((row >> 2) & 3)) << 4);
         // blocked: the lane's word of unit row / 32 holds both 32-k steps (picked by ABID); row-major: [row][8 bytes]
-        m_off[a] = C::A_BYTES + C::B_BYTES + (blocked ? (row >> 5) * 256 + lane * 4 : FP8 ? row * 16 + 4 * lh : row * 8 + 2 * lh);
+        m_off[a] = C::A_BYTES + C::B_BYTES + (FP8 ? row * 16 + 4 * lh : blocked ? (row >> 5) * 256 + lane * 4 : row * 8 + 2 * lh);
     }
 #pragma unroll
     for (int b = 0; b < FN; ++b) {
@@ -601,8 +602,9 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                 uint32_t* vals_p = reinterpret_cast<uint32_t*>(ep.vals) + ((int64_t)(t0 + (lane >> 3)) * (F / 4) + blk_g * 2) / 2;
                 uint32_t* kept_p = reinterpret_cast<uint32_t*>(ep.ykept) + ykept_off(t0 + (lane >> 3), blk_g, F);
                 uint8_t* meta_p = ep.meta + (int64_t)(t0 + (lane >> 3)) * (F / 16) + (blk_g >> 1);
-                uint16_t* v24_p = ep.v24 + blk_off(t0 + (lane >> 3), blk_g * 4, F / 64);
-                uint8_t* m24_p = ep.m24 + mblk_off(t0 + (lane >> 3), blk_g * 8, F / 64);
+                // fp8: v24 holds pairs of codes (4 codes per block = 2 pairs), m24 is row-major [T, F / 8]
+                uint16_t* v24_p = FP8 ? ep.v24 + blk_off(t0 + (lane >> 3), blk_g * 2, F / 128) : ep.v24 + blk_off(t0 + (lane >> 3), blk_g * 4, F / 64);
+                uint8_t* m24_p = FP8 ? ep.m24 + (int64_t)(t0 + (lane >> 3)) * (F / 8) + blk_g : ep.m24 + mblk_off(t0 + (lane >> 3), blk_g * 8, F / 64);
                 const uint32_t c0 = (cw & 0xFFu) * 2, c1 = ((cw >> 8) & 0xFFu) * 2, c2 = ((cw >> 16) & 0xFFu) * 2, c3 = (cw >> 24) * 2;
                 uint32_t pre_m[8], pre_y[8];                                // EPI 2: saved metadata and y1 of the 8 sweeps, fetched together
                 if (EPI == 2 && valid) {
@@ -627,7 +629,10 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             const uint32_t p0 = nib & 3u, p1 = nib >> 2;
                             const uint32_t k0 = (p0 == 0) ? y0 : (p0 == 1) ? y1 : y2;
                             const uint32_t k1 = (p1 == 3) ? y3 : (p1 == 2) ? y2 : y1;
-                            vals_p[(int64_t)it * 8 * (F / 8)] = v;
+                            if (FP8)    // canonical values are the survivors' codes [T, F / 4]
+                                reinterpret_cast<uint16_t*>(ep.vals)[(int64_t)(t0 + t) * (F / 8) + blk_g] = (uint16_t)fp8_enc2(bf2f(v & 0xFFFFu), bf2f(v >> 16), ep.inv_out);
+                            else
+                                vals_p[(int64_t)it * 8 * (F / 8)] = v;
                             kept_p[it * 64] = k0 | (k1 << 16);
                             // metadata bytes of the row's 8 blocks -> one 32-bit store from the lane of block 0
                             uint32_t mw = nib | (row_shl<1>(nib) << 4);
@@ -650,9 +655,18 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         if (ep.v24) {       // (not wanted when eq. (7) gathers rows from the canonical arrays)
                             uint32_t a24, b24, mb8;
                             vnm_block_to_24(v, nib, cw, a24, b24, mb8);
+                            if (FP8) {      // the survivors' codes (an empty slot is code 0 = +0); four blocks' metadata bytes in one store
+                                const uint32_t qa = fp8_enc2(bf2f(a24 & 0xFFFFu), bf2f(a24 >> 16), ep.inv_out);
+                                const uint32_t qb = fp8_enc2(bf2f(b24 & 0xFFFFu), bf2f(b24 >> 16), ep.inv_out);
+                                *reinterpret_cast<uint32_t*>(v24_p + (int64_t)(it >> 1) * (F / 128) * 512 + (it & 1) * 256) = qa | (qb << 16);
+                                uint32_t m4 = mb8 | (row_shl<1>(mb8) << 8);
+                                m4 |= row_shl<2>(m4) << 16;
+                                if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(m24_p + (int64_t)it * 8 * (F / 8)) = m4;
+                            } else {
                             const uint32_t m2 = mb8 | (row_shl<1>(mb8) << 8);     // two column blocks = 16 k = one lane's half-word of a unit
                             *reinterpret_cast<uint2*>(v24_p + (int64_t)(it >> 1) * (F / 64) * 512 + (it & 1) * 256) = make_uint2(a24, b24);
                             if ((lane & 1) == 0) *reinterpret_cast<uint16_t*>(m24_p + (int64_t)(it >> 2) * (F / 64) * 256 + (it & 3) * 32) = (uint16_t)m2;
+                            }
                         }
                         // transposed tile for the weight-gradient GEMM, compacted to the block's four kept hidden units:
                         // row = 4 * block + position among the kept units, column = token
@@ -755,6 +769,24 @@ hipError_t launch_spmm24_fp8(const uint8_t* a_codes, const uint8_t* a_meta, cons
     else
         hipLaunchKernelGGL((gemm_nt_v2_kernel<true, false, 0, false, true>), grid, dim3(512), 0, s, a, a_meta, b, bias, (int)Ra, (int)Rb, (int)(K / 2), out, ldo,
                            tiles_m, tiles_n, none, g, alpha);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* Bq, const float* bias, float alpha, int64_t Ra,
+                                   int64_t Rb, int64_t K, uint16_t* out, int64_t ldo, const VnmEpilogue* ep, hipStream_t s) {
+    if (K % 128 != 0 || (ep && ep->mode != 1 && ep->mode != 2)) return hipErrorInvalidValue;
+    const int tiles_m = (int)((Ra + 255) / 256), tiles_n = (int)((Rb + 255) / 256);
+    const VnmEpilogue e = ep ? *ep : VnmEpilogue();
+    const GemmGroup g;
+    dim3 grid((unsigned)(tiles_m * tiles_n));
+    const uint16_t* a = reinterpret_cast<const uint16_t*>(a_codes);
+    const uint16_t* b = reinterpret_cast<const uint16_t*>(Bq);
+#define SFFN_F8(ICONTIG, E) hipLaunchKernelGGL((gemm_nt_v2_kernel<true, ICONTIG, E, true, true>), grid, dim3(512), 0, s, a, a_meta, b, bias, (int)Ra, (int)Rb, \
+                                              (int)(K / 2), out, ldo, tiles_m, tiles_n, e, g, alpha)
+    if (!ep) SFFN_F8(false, 0);
+    else if (ep->mode == 1) SFFN_F8(true, 1);
+    else SFFN_F8(true, 2);
+#undef SFFN_F8
     return hipGetLastError();
 }
 

@@ -35,6 +35,10 @@ struct VnmEpilogue {
     //        canonical arrays).
     const int32_t* perm = nullptr;
     int logM = 3;
+    // fp8 operands (launch_gemm_fp8_blocked, modes 1 / 2): the survivors leave as E4M3 codes quantised with 1 / scale = inv_out: mode 1 writes
+    // vals as codes [T, F / 4] and v24 / m24 as a 2:4 code matrix (v24: pairs of codes in the blocked layout, m24: row-major [T, F / 8]);
+    // mode 2 keeps vals = dy1 in bf16 and writes v24 as codes.  ykept, at, kmask, colidx, meta stay as in the bf16 modes.
+    float inv_out = 1.0f;
 };
 
 // Grouped (mixture-of-experts) form of a contraction: the token axis is cut into n consecutive segments, one per
@@ -152,6 +156,18 @@ hipError_t launch_transpose_u8(const uint8_t* in, int64_t R, int64_t C, int64_t 
 // [Ra, K/2] + metadata [Ra, K/8], B codes [Rb, K], both row-major; K a multiple of 128; out bf16 as launch_gemm_nt.
 hipError_t launch_spmm24_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* Bq, const float* bias, float alpha, int64_t Ra, int64_t Rb,
                              int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
+
+// The same contraction on operands in the blocked layout with a pair of codes per 2-byte element (the fused fp8 step): a_codes = packed 2:4
+// codes [Ra, K/2], a_meta row-major [Ra, K/8], Bq = codes [Rb, K].  ep = nullptr: out[i * ldo + j] (eqs. (3), (7): Ra = tokens);
+// ep (mode 1 or 2, M = 8): eq. (1) / eq. (4) with the fused V:N:M epilogue, Ra = hidden units, Rb = tokens, out [T, F] if ep->store_dense.
+hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* Bq, const float* bias, float alpha, int64_t Ra,
+                                   int64_t Rb, int64_t K, uint16_t* out, int64_t ldo, const VnmEpilogue* ep, hipStream_t s);
+// fp8.hip, producers of such operands: quantised copy in the same orientation / transposed; 2:4 pruning that also writes the blocked codes
+hipError_t launch_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_blk, hipStream_t s);
+hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s);
+// (src_q_blk, trans = 1 only: also the unpruned source quantised in its own orientation, [K rows, R codes])
+hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
+                                   uint8_t* codes_blk, hipStream_t s, uint8_t* src_q_blk = nullptr);
 
 hipError_t launch_wgrad_vnm(const uint16_t* atc, const uint8_t* kmask, const uint16_t* G, int64_t F, int64_t N, int64_t T,
                             int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);

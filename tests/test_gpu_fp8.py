@@ -160,3 +160,78 @@ def test_fp8_forward_chain_at_the_1b_shape():
         w2q_ref = fp8.quantize_fp8(inp["W2"], sw2)
         assert_gemm_close(to_bits(y3)[r], fp8.vnm_spmm_fp8(oc, om, oi, sy, w2q_ref, sw2, 0), "fp8 y3 block")
     assert 0 < float(amax.cpu()[0]) < 1e4
+
+
+# ---- the whole step with fp8 operands (ffn_sparse_step_fp8) --------------------------------------------------------------------
+def _fp8_step_scales(inp):
+    """Delayed-scaling stand-in: amax / 448 of each quantised tensor, taken from the oracle's bf16 step on the same inputs."""
+    ref = oracle.ffn_sparse_step_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"])
+    amax = lambda b: float(np.max(np.abs(oracle.bits_to_f32(b))))
+    return dict(x=amax(inp["X"]) / 448, w1=amax(inp["W1"]) / 448, w2=amax(inp["W2"]) / 448, y2=max(amax(oracle.sqrelu(ref["y1"])), 1e-6) / 448,
+                dy=amax(inp["dY"]) / 448, dy1=max(amax(ref["dy1_vals"]), 1e-6) / 448)
+
+
+def _check_fp8_step_against_oracle(inp, sc, s, outs, mode):
+    """Teacher-forced: every oracle stage consumes the GPU's output of the stage before it."""
+    f8 = oracle.fp8
+    T, F = s["y1"].shape
+    c1, m1 = f8.prune24_compress_fp8(inp["W1"], sc["w1"], mode)
+    assert np.array_equal(s["w1_meta"], m1) and np.array_equal(s["w1_codes"], c1)
+    xq = f8.quantize_fp8(inp["X"], sc["x"])
+    assert_gemm_close(s["y1"], f8.spmm24_fp8(xq, sc["x"], c1, m1, sc["w1"], inp["b1"]), "y1")
+    yc, ym, cix = f8.sqrelu_vnm_compress_fp8(s["y1"], sc["y2"])
+    assert np.array_equal(s["colidx"], cix) and np.array_equal(s["y2_meta"], ym) and np.array_equal(s["y2_codes"], yc)
+    yv, ym_b, cix_b = oracle.sqrelu_vnm_compress(s["y1"])                 # the bf16 survivors (weight gradients, y1_kept)
+    assert np.array_equal(ym_b, ym) and np.array_equal(cix_b, cix)
+    ones = np.arange(1, yv.size + 1, dtype=np.uint32).reshape(yv.shape)
+    slot_of = oracle.vnm_decompress((ones & 0xFFFF).astype(np.uint16), ym, cix).astype(np.int64) \
+        + (oracle.vnm_decompress((ones >> 16).astype(np.uint16), ym, cix).astype(np.int64) << 16)
+    want_kept = np.zeros(yv.size, dtype=np.uint16)
+    tt, ff = np.nonzero(slot_of)
+    want_kept[slot_of[tt, ff] - 1] = s["y1"][tt, ff]
+    want_kept = want_kept.reshape(T // 64, 64, F // 64, 8, 2).transpose(0, 2, 1, 3, 4)
+    assert np.array_equal(s["y1_kept"].reshape(-1), want_kept.reshape(-1))
+    assert_gemm_close(outs["Y3"], f8.vnm_spmm_fp8(yc, ym, cix, sc["y2"], f8.quantize_fp8(inp["W2"], sc["w2"]), sc["w2"], 0), "y3")
+    c2, m2 = f8.prune24_compress_fp8(np.ascontiguousarray(inp["W2"].T), sc["w2"], mode)
+    assert np.array_equal(s["w2t_meta"], m2) and np.array_equal(s["w2t_codes"], c2)
+    assert_gemm_close(s["dy2"], f8.spmm24_fp8(f8.quantize_fp8(inp["dY"], sc["dy"]), sc["dy"], c2, m2, sc["w2"], None), "dy2")
+    dv = oracle.dsqrelu_vnm(s["dy2"], s["y1"], ym, cix)
+    assert np.array_equal(s["dy1_vals"], dv)
+    assert_gemm_close(outs["dW2"], oracle.vnm_wgrad(yv, ym, cix, inp["dY"], 0), "dW2")
+    assert_gemm_close(outs["dX"], f8.vnm_spmm_fp8(f8.quantize_fp8(dv, sc["dy1"]), ym, cix, sc["dy1"], f8.quantize_fp8(inp["W1"], sc["w1"]), sc["w1"], 1), "dX")
+    assert_gemm_close(outs["dW1"], oracle.vnm_wgrad(dv, ym, cix, inp["X"], 1), "dW1")
+
+
+@pytest.mark.parametrize("T,D,F,mode,seed", [(64, 128, 128, sffn.MODE_HARD, 0), (512, 256, 1024, sffn.MODE_HARD, 0), (512, 256, 1024, sffn.MODE_SOFT, 1),
+                                             (192, 384, 640, sffn.MODE_SOFT, 2)])
+def test_ffn_sparse_step_fp8(T, D, F, mode, seed):
+    """The fused fp8 step, teacher-forced stage by stage; then the timed configuration (no dense y1 / dy2) must give the same bits."""
+    from workload import make_ffn_inputs
+    inp = make_ffn_inputs(T, D, F, seed=seed)
+    sc = _fp8_step_scales(inp)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    step = sffn.FfnStepFp8(T, D, F, sc, mode, keep_dense=True)
+    outs = step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    torch.cuda.synchronize()
+    s = {k: to_bits(v) if v.dtype == torch.bfloat16 else v.cpu().numpy() for k, v in step.saved().items()}
+    o = {k: to_bits(v) for k, v in zip(("Y3", "dX", "dW1", "dW2"), outs)}
+    _check_fp8_step_against_oracle(inp, sc, s, o, mode)
+    fast = sffn.FfnStepFp8(T, D, F, sc, mode)
+    outs2 = fast(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    torch.cuda.synchronize()
+    for k, v in zip(("Y3", "dX", "dW1", "dW2"), outs2):
+        assert np.array_equal(to_bits(v), o[k]), k
+    s2 = fast.saved()
+    for k in ("y2_codes", "y2_meta", "colidx", "w1_codes", "w2t_codes"):
+        assert np.array_equal(s2[k].cpu().numpy(), s[k]), k
+    assert np.array_equal(to_bits(s2["dy1_vals"]), s["dy1_vals"]) and np.array_equal(to_bits(s2["y1_kept"]), s["y1_kept"])
+
+
+def test_ffn_sparse_step_fp8_rejects_what_it_does_not_cover():
+    from paper_2602_06183_amd import binding
+    with pytest.raises(sffn.SffnError):
+        sffn.FfnStepFp8(64, 64, 128, dict(x=1, w1=1, w2=1, y2=1, dy=1, dy1=1))               # D not a multiple of 128
+    step = sffn.FfnStepFp8(64, 128, 128, dict(x=1, w1=1, w2=1, y2=0.0, dy=1, dy1=1))
+    z = lambda *shape: torch.zeros(shape, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sffn.SffnError):
+        step(z(64, 128), z(128, 128), z(128, 128), None, z(64, 128))                          # a zero scale

@@ -327,3 +327,53 @@ def test_full_size_router_step(name, M):
         for packed, G, got in ((sv["vals"], inp["dY"], np.ascontiguousarray(dW2[:, f].T)), (sv["dvals"], inp["X"], dW1[f])):
             a = oracle.bits_to_f64(oracle.prune24_decompress(packed[real], sv["meta"][real])[:, js])
             assert_gemm_close(got, oracle.f64_to_bits(a.T @ oracle.bits_to_f64(G[perm[real]])), "wgrad rows")
+
+
+def test_full_size_fp8_step():
+    """ffn_sparse_step_fp8 at the 1B layer in the timed configuration: packed outputs bit-exact against the oracle's compressors on
+    the kept y1, contractions on sampled rows / columns against the oracle's fp8 contractions (teacher-forced on the GPU's packed operands)."""
+    from oracle import fp8 as f8
+    T, D, F = CONFIGS["1b"]
+    inp = make_ffn_inputs(T, D, F, seed=0)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    ref_step = sffn.FfnStep(T, D, F)
+    ref_step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    sv = ref_step.saved()
+    amax = lambda t: float(t.float().abs().max())
+    sc = dict(x=amax(dev["X"]) / 448, w1=amax(dev["W1"]) / 448, w2=amax(dev["W2"]) / 448, y2=amax(sv["y2_vals"]) / 448, dy=amax(dev["dY"]) / 448,
+              dy1=amax(sv["dy1_vals"]) / 448)
+    del ref_step, sv
+    step = sffn.FfnStepFp8(T, D, F, sc)
+    Y3, dX, dW1, dW2 = (to_bits(t) for t in step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"]))
+    s = {k: (to_bits(v) if v.dtype == torch.bfloat16 else v.cpu().numpy()) for k, v in step.saved().items()}
+    c1, m1 = f8.prune24_compress_fp8(inp["W1"], sc["w1"])
+    assert np.array_equal(s["w1_codes"], c1) and np.array_equal(s["w1_meta"], m1)
+    c2, m2 = f8.prune24_compress_fp8(np.ascontiguousarray(inp["W2"].T), sc["w2"])
+    assert np.array_equal(s["w2t_codes"], c2) and np.array_equal(s["w2t_meta"], m2)
+    rng = np.random.default_rng(0)
+    rows = np.sort(rng.choice(T // 64, 6, replace=False))[:, None] * 64 + np.arange(64)[None, :]      # six whole 64-token blocks
+    rows = rows.reshape(-1)
+    # y1 on those token blocks from the oracle's eq. (1); the GPU's packed y2 must be the compression of a y1 within tolerance of it:
+    # checked through the kept y1 (bit-exact bookkeeping) and the downstream contractions
+    xq = f8.quantize_fp8(inp["X"][rows], sc["x"])
+    y1_ref = f8.spmm24_fp8(xq, sc["x"], c1, m1, sc["w1"], inp["b1"])
+    yc, ym, cix = s["y2_codes"][rows], s["y2_meta"][rows], s["colidx"][rows[::64] // 64]
+    # the GPU's survivors sit where the GPU's own y1 put them; their codes must decode to y2 values of the reference y1 within fp8 spacing
+    dec = oracle.vnm_decompress(f8.codes_as_bf16_bits(yc), ym, cix)
+    y2_ref = oracle.bits_to_f32(oracle.sqrelu(y1_ref))
+    got = oracle.bits_to_f32(dec) * np.float32(sc["y2"])
+    nz = got != 0
+    assert nz.mean() > 0.01
+    # half an E4M3 spacing (2^-4 relative, 2^-10 absolute in code units) plus y1's bf16 rounding carried through the square
+    assert np.all(np.abs(got[nz] - y2_ref[nz]) <= (2.0 ** -4 + 2.0 ** -6) * np.abs(y2_ref[nz]) + 2.0 ** -9 * sc["y2"])
+    w2q = f8.quantize_fp8(inp["W2"], sc["w2"])
+    assert_gemm_close(Y3[rows], f8.vnm_spmm_fp8(yc, ym, cix, sc["y2"], w2q, sc["w2"], 0), "y3")
+    dv = s["dy1_vals"][rows]
+    w1q = f8.quantize_fp8(inp["W1"], sc["w1"])
+    assert_gemm_close(dX[rows], f8.vnm_spmm_fp8(f8.quantize_fp8(dv, sc["dy1"]), ym, cix, sc["dy1"], w1q, sc["w1"], 1), "dX")
+    # weight gradients: bf16 contractions over all tokens for sampled hidden units; y2's bf16 survivors are not stored, so eq. (8) only
+    cols = np.sort(rng.choice(F // 8, 8, replace=False))[:, None] * 8 + np.arange(8)[None, :]
+    cols = cols.reshape(-1)
+    dense_dy1 = oracle.vnm_decompress(s["dy1_vals"], s["y2_meta"], s["colidx"])[:, cols]
+    want = oracle.dense_nt(np.ascontiguousarray(dense_dy1.T), np.ascontiguousarray(inp["X"].T))
+    assert_gemm_close(dW1[cols], want, "dW1")
