@@ -322,19 +322,22 @@ def main():
             amax = lambda t: max(float(t.float().abs().max()), 1e-12)
             sc = dict(x=amax(hw.X) / 448, w1=amax(hw.W1) / 448, w2=amax(hw.W2) / 448, y2=amax(sv["y2_vals"]) / 448, dy=amax(hw.dY) / 448,
                       dy1=amax(sv["dy1_vals"]) / 448)
-            st8 = sffn.FfnStepFp8(hw.T, hw.D, hw.F, sc, mode)
-            run8 = lambda: st8(hw.X, hw.W1, hw.W2, hw.b1, hw.dY)
-            for _ in range(ewarm):
-                run8()
-            ms8 = timed(run8, esteps)
             ms16 = timed(hw.sparse_step, esteps)
             msd = timed(hw.dense_step, esteps)
-            tf8 = hw.flops / (ms8 * 1e-3) / 1e12
-            fp8_step = {"workload": hw.name, "ms_per_step": round(ms8, 4), "bf16_sparse_ms_per_step": round(ms16, 4), "dense_bf16_ms_per_step": round(msd, 4),
-                        "speedup_vs_dense_bf16": round(msd / ms8, 4), "speedup_vs_sparse_bf16": round(ms16 / ms8, 4),
-                        "tflops_dense_equiv": round(tf8, 2), "operands": "E4M3 codes in eqs. (1), (3), (4), (7), quantised inside the pruning passes and the "
-                        "V:N:M epilogues; eqs. (5), (8) bf16; six per-tensor scales = amax / 448"}
-            del st8, sv
+            fp8_step = {"workload": hw.name, "bf16_sparse_ms_per_step": round(ms16, 4), "dense_bf16_ms_per_step": round(msd, 4),
+                        "operands": "E4M3 codes in eqs. (1), (3), (4), (7), quantised inside the pruning passes and the V:N:M epilogues; "
+                                    "six per-tensor scales = amax / 448; weight gradients (eqs. (5), (8)) in bf16, or on the same codes (fp8_weight_gradients)"}
+            for name8, w8 in (("bf16_weight_gradients", False), ("fp8_weight_gradients", True)):
+                st8 = sffn.FfnStepFp8(hw.T, hw.D, hw.F, sc, mode, wgrad_fp8=w8)
+                run8 = lambda: st8(hw.X, hw.W1, hw.W2, hw.b1, hw.dY)
+                for _ in range(ewarm):
+                    run8()
+                ms8 = timed(run8, esteps)
+                fp8_step[name8] = {"ms_per_step": round(ms8, 4), "speedup_vs_dense_bf16": round(msd / ms8, 4), "speedup_vs_sparse_bf16": round(ms16 / ms8, 4),
+                                   "tflops_dense_equiv": round(hw.flops / (ms8 * 1e-3) / 1e12, 2)}
+                del st8
+                free()
+            del sv
             free()
         # configs[3]'s sweep of the ReLU zero fraction: same tensors, only the bias shifts
         if hw.name == "70b":

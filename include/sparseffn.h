@@ -69,6 +69,7 @@ typedef struct sffn_cfg {
  * HBM, 15 launches).  It is what the fused path is checked against bit for bit; shapes the gathered-row kernel does not cover
  * (4 F / M not a multiple of 64 or above 7168) take it in any case. */
 #define SFFN_FLAG_UNFUSED 2
+#define SFFN_FLAG_FP8_WGRAD 4     /* ffn_sparse_step_fp8 only: eqs. (5), (8) on codes as well */
 
 /* Byte offsets, inside the workspace of ffn_sparse_step, of the tensors Alg. 2 line 1 saves
  * from the forward pass and of the other intermediates (all filled when the step returns). */
@@ -192,7 +193,9 @@ int vnm_spmm_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* a
  * the epilogues of eqs. (1) / (4).  Everything that decides a position stays bf16 (y1, y2, the column scores, the 2:4 choices,
  * eq. (6)), so metadata and column indices are those the bf16 rules give on this step's own y1; the weight gradients (eqs. (5),
  * (8)) are the bf16 contractions on the bf16 survivors.  out = bf16( (sum dec * dec) * (scale_a * scale_b) [+ b1] ).
- * Shapes: V = 64, M = 8, T a multiple of 64, D and F multiples of 128; cfg->flags: SFFN_FLAG_KEEP_DENSE or 0.
+ * With SFFN_FLAG_FP8_WGRAD the weight gradients also contract codes, the ones the forward / input-gradient contractions already use:
+ * dW2 = bf16( (sum_t dec(y2q[t,f]) dec(dYq[t,d])) * (s_y2 s_dy) ), dW1 = bf16( (sum_t dec(dy1q[t,f]) dec(Xq[t,d])) * (s_dy1 s_x) ).
+ * Shapes: V = 64, M = 8, T a multiple of 64, D and F multiples of 128; cfg->flags: any of SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD.
  * Workspace: sffn_fp8_workspace_bytes(cfg); after the call it holds, at the offsets of sffn_fp8_workspace_layout: the pruned
  * weights (codes [F, D/2] u8 + meta [F, D/8]), y2 (codes [T, F/4] u8, meta [T, F/16], colidx [T/64, F/8, 4]), dy1 at y2's slots
  * (bf16 [T, F/4]), y1 at y2's slots (y1_kept, runs of 64 tokens x 8 blocks as in ffn_sparse_step) and, with KEEP_DENSE, y1 / dy2. */

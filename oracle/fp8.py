@@ -154,7 +154,17 @@ def vnm_spmm_fp8(a_codes, a_meta, a_colidx, scale_a, wq, scale_w, w_kmajor, V=64
     return _finish(bits_to_f32(a).astype(np.float64) @ w.T, scale_a, scale_w, None)
 
 
-def ffn_sparse_step_fp8_ref(X, W1, W2, b1, dY, scales, mode=HARD, V=64, M=8):
+def vnm_wgrad_fp8(a_codes, a_meta, a_colidx, scale_a, gq, scale_g, out_f_major, V=64, M=8):
+    """eq. (5) / eq. (8) on fp8 operands: out[f, n] (out_f_major = 1) or out[n, f] (0) = bf16( (sum_t dec(Av[t, f]) dec(G[t, n])) scale_a scale_g ),
+    Av = the V:N:M code matrix, gq = codes of G [T, N].  The sum is exact (float64 on exactly decoded values)."""
+    a = bits_to_f32(vnm_decompress(codes_as_bf16_bits(a_codes), a_meta, a_colidx, V, M)).astype(np.float64)       # [T, F]
+    acc = a.T @ e4m3_decode(gq).astype(np.float64)                                                                # [F, N]
+    if not out_f_major:
+        acc = acc.T
+    return f64_to_bits(acc * np.float64(np.float32(scale_a) * np.float32(scale_g)))
+
+
+def ffn_sparse_step_fp8_ref(X, W1, W2, b1, dY, scales, mode=HARD, V=64, M=8, wgrad_fp8=False):
     """Alg. 1 + Alg. 2 with fp8 operands in the four contractions whose sparse operand is 2:4 along the contraction
     (eqs. (1), (3), (4), (7)); a stated reading built from the functions above, in the paper's order.
 
@@ -164,7 +174,8 @@ def ffn_sparse_step_fp8_ref(X, W1, W2, b1, dY, scales, mode=HARD, V=64, M=8):
     Everything that decides a position stays bf16: y1 is the bf16 output of eq. (1), y2 = bf16(max(y1, 0)^2) picks the
     columns and the per-row survivors, eq. (6) is evaluated in bf16 arithmetic on the bf16 dy2 and y1 exactly as in the
     bf16 step, and only then are the survivors quantised for the next contraction.  The weight gradients (eqs. (5), (8),
-    contraction over tokens) stay bf16 on the bf16 survivors and the bf16 dY / X."""
+    contraction over tokens) stay bf16 on the bf16 survivors and the bf16 dY / X, unless wgrad_fp8: then they contract the
+    codes that eqs. (3) / (7) and eqs. (4) / (1) already use (y2 and dY for eq. (5), dy1 and X for eq. (8)), with those tensors' scales."""
     s = {k: np.float32(v) for k, v in scales.items()}
     xq = quantize_fp8(X, s["x"])
     w1_codes, w1_meta = prune24_compress_fp8(W1, s["w1"], mode)
@@ -183,6 +194,9 @@ def ffn_sparse_step_fp8_ref(X, W1, W2, b1, dY, scales, mode=HARD, V=64, M=8):
     w1q = quantize_fp8(W1, s["w1"])
     dX = vnm_spmm_fp8(dy1_codes, y2_meta, colidx, s["dy1"], w1q, s["w1"], 1, V, M)    # Alg. 2 line 5
     dW1 = vnm_wgrad(dy1_vals, y2_meta, colidx, X, 1, V, M)                            # Alg. 2 line 6 (bf16)
+    if wgrad_fp8:
+        dW2 = vnm_wgrad_fp8(y2_codes, y2_meta, colidx, s["y2"], dyq, s["dy"], 0, V, M)
+        dW1 = vnm_wgrad_fp8(dy1_codes, y2_meta, colidx, s["dy1"], xq, s["x"], 1, V, M)
     return dict(xq=xq, w1_codes=w1_codes, w1_meta=w1_meta, y1=y1, y2_codes=y2_codes, y2_vals=y2_vals, y2_meta=y2_meta, colidx=colidx,
                 w2q=w2q, y3=y3, dyq=dyq, w2t_codes=w2t_codes, w2t_meta=w2t_meta, dy2=dy2, dW2=dW2, dy1_vals=dy1_vals,
                 dy1_codes=dy1_codes, w1q=w1q, dX=dX, dW1=dW1)

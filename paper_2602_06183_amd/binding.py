@@ -183,6 +183,7 @@ def profile_read():
 
 FLAG_KEEP_DENSE = 1
 FLAG_UNFUSED = 2
+FLAG_FP8_WGRAD = 4
 
 
 def dense_sqrelu(y1, out):
@@ -519,9 +520,10 @@ class FfnStepFp8:
     """ffn_sparse_step_fp8 with outputs and workspace allocated once.  scales: dict with the six per-tensor scales
     x, w1, w2, y2, dy, dy1 (positive floats; delayed scaling: the caller derives them from earlier steps)."""
 
-    def __init__(self, T, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False):
+    def __init__(self, T, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False):
+        """wgrad_fp8: eqs. (5), (8) contract codes as well (SFFN_FLAG_FP8_WGRAD); otherwise they are the bf16 contractions."""
         self.T, self.D, self.F, self.mode = T, D, F, mode
-        self.cfg = _cfg(T, D, F, mode, M=8, flags=FLAG_KEEP_DENSE if keep_dense else 0)
+        self.cfg = _cfg(T, D, F, mode, M=8, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0))
         self.scales = _Fp8Scales(*[float(scales[k]) for k in ("x", "w1", "w2", "y2", "dy", "dy1")])
         lay = _Fp8Layout()
         _check(load().sffn_fp8_workspace_layout(ctypes.byref(self.cfg), ctypes.byref(lay)))

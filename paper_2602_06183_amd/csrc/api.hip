@@ -386,7 +386,7 @@ struct Fp8Layout {
 };
 bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L) {
     if (!c || !mult64(c->T) || !mult128(c->D) || !mult128(c->F) || c->V != 64 || c->M != 8) return false;
-    if (c->flags & ~SFFN_FLAG_KEEP_DENSE) return false;
+    if (c->flags & ~(SFFN_FLAG_KEEP_DENSE | SFFN_FLAG_FP8_WGRAD)) return false;
     const bool dense = (c->flags & SFFN_FLAG_KEEP_DENSE) != 0;
     const size_t T = c->T, D = c->D, F = c->F, TF = T * F;
     size_t off = 0;
@@ -417,7 +417,7 @@ size_t sffn_fp8_workspace_bytes(const sffn_cfg* cfg) {
 int sffn_fp8_workspace_layout(const sffn_cfg* cfg, sffn_fp8_ws_layout* out) {
     Fp8Layout L;
     REQUIRE(out != nullptr, SFFN_EINVAL, "sffn_fp8_workspace_layout: out is null");
-    REQUIRE(make_fp8_layout(cfg, &L), SFFN_EINVAL, "sffn_fp8_workspace_layout: T a multiple of 64, D and F of 128, V = 64, M = 8, flags: SFFN_FLAG_KEEP_DENSE only");
+    REQUIRE(make_fp8_layout(cfg, &L), SFFN_EINVAL, "sffn_fp8_workspace_layout: T a multiple of 64, D and F of 128, V = 64, M = 8, flags: SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD");
     *out = L.pub;
     return SFFN_OK;
 }
@@ -427,7 +427,7 @@ int ffn_sparse_step_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* sc, const ui
     REQUIRE(cfg != nullptr && sc != nullptr, SFFN_EINVAL, "ffn_sparse_step_fp8: cfg or scales is null");
     Fp8Layout L;
     REQUIRE(cfg->M == 8 && cfg->V == 64, SFFN_EUNSUPPORTED, "ffn_sparse_step_fp8: only V = 64, M = 8 is built");
-    REQUIRE(make_fp8_layout(cfg, &L), SFFN_EINVAL, "ffn_sparse_step_fp8: T must be a positive multiple of 64, D and F of 128; flags: SFFN_FLAG_KEEP_DENSE only");
+    REQUIRE(make_fp8_layout(cfg, &L), SFFN_EINVAL, "ffn_sparse_step_fp8: T must be a positive multiple of 64, D and F of 128; flags: SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD");
     REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_sparse_step_fp8: unknown mode");
     REQUIRE(X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_sparse_step_fp8: null pointer");
     REQUIRE(aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(dY) && aligned16(Y3) && aligned16(dX) && aligned16(dW1) && aligned16(dW2) &&
@@ -447,33 +447,38 @@ int ffn_sparse_step_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* sc, const ui
     uint16_t *xtb = (uint16_t*)(ws + L.xt_blk), *dytb = (uint16_t*)(ws + L.dyt_blk), *atb = (uint16_t*)(ws + L.at_blk);
     uint8_t *v24 = ws + L.v24, *m24 = ws + L.m24, *kmask = ws + L.kmask;
     const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
+    const bool w8 = (cfg->flags & SFFN_FLAG_FP8_WGRAD) != 0;      // eqs. (5), (8) on codes too: X.T, dY.T and the compact transposed survivors as codes
     const float ix = 1.0f / sc->x, iw1 = 1.0f / sc->w1, iw2 = 1.0f / sc->w2, idy = 1.0f / sc->dy;
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
     // ---- Alg. 1 -------------------------------------------------------------------------------
-    STAGE(launch_transpose(X, T, D, D, xtb, 1, nullptr, s), "step/X.T");                                    // bf16, for eq. (8)
+    if (w8) STAGE(launch_transpose_quantize_fp8_blocked(X, T, D, D, ix, (uint8_t*)xtb, s), "step/quantize(X.T)");     // codes, for eq. (8)
+    else    STAGE(launch_transpose(X, T, D, D, xtb, 1, nullptr, s), "step/X.T");                            // bf16, for eq. (8)
     STAGE(launch_quantize_fp8_blocked(X, T, D, D, ix, xq, s), "step/quantize(X)");
     STAGE(launch_prune24_fp8_step(W1, F, D, D, 0, cfg->mode, iw1, w1c, w1m, w1b, s), "step/prune24_fp8(W1)");
     {   // eq. (1) on codes, then eq. (2) + V:N:M compression on the bf16 tile; the survivors leave as codes (and in bf16 for eq. (5))
         VnmEpilogue ep;
         ep.mode = 1; ep.store_dense = keep_dense; ep.vals = (uint16_t*)y2c; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
-        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->y2;
+        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->y2; ep.at_fp8 = w8;
         STAGE(launch_gemm_fp8_blocked(w1b, w1m, xq, b1, sc->x * sc->w1, F, T, D, y1, F, &ep, s), "step/y1+sqrelu_vnm_compress");
     }
     STAGE(launch_prune24_fp8_step(W2, F, D, F, 1, cfg->mode, iw2, w2c, w2m, w2b, s, w2q), "step/prune24_fp8(W2.T)+quantize(W2)");
     STAGE(launch_gemm_fp8_blocked(v24, m24, w2q, nullptr, sc->y2 * sc->w2, T, D, F, Y3, D, nullptr, s), "step/y3");      // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
-    STAGE(launch_transpose(dY, T, D, D, dytb, 1, nullptr, s), "step/dY.T");                                 // bf16, for eq. (5)
+    if (w8) STAGE(launch_transpose_quantize_fp8_blocked(dY, T, D, D, idy, (uint8_t*)dytb, s), "step/quantize(dY.T)");
+    else    STAGE(launch_transpose(dY, T, D, D, dytb, 1, nullptr, s), "step/dY.T");                         // bf16, for eq. (5)
     STAGE(launch_quantize_fp8_blocked(dY, T, D, D, idy, dyq, s), "step/quantize(dY)");
-    STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, nullptr), "step/dW2");                  // eq. (5), bf16
+    if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)dytb, sc->y2 * sc->dy, F, D, T, 1, dW2, F, s), "step/dW2");   // eq. (5) on codes
+    else    STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, nullptr), "step/dW2");          // eq. (5), bf16
     {   // eq. (4) on codes, then eq. (6) in bf16 on y2's kept slots; dy1 leaves in bf16 (canonical, eq. (8)) and as codes (eq. (7))
         VnmEpilogue ep;
         ep.mode = 2; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
-        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->dy1;
+        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->dy1; ep.at_fp8 = w8;
         STAGE(launch_gemm_fp8_blocked(w2b, w2m, dyq, nullptr, sc->dy * sc->w2, F, T, D, dy2, F, &ep, s), "step/dy2+dsqrelu_vnm");
     }
     STAGE(launch_transpose_quantize_fp8_blocked(W1, F, D, D, iw1, w1tq, s), "step/quantize(W1.T)");
     STAGE(launch_gemm_fp8_blocked(v24, m24, w1tq, nullptr, sc->dy1 * sc->w1, T, D, F, dX, D, nullptr, s), "step/dX");      // eq. (7)
-    STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, nullptr), "step/dW1");                   // eq. (8), bf16
+    if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)xtb, sc->dy1 * sc->x, F, D, T, 0, dW1, D, s), "step/dW1");   // eq. (8) on codes
+    else    STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, nullptr), "step/dW1");           // eq. (8), bf16
     return SFFN_OK;
 }
 

@@ -678,8 +678,15 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {          // 2 groups of 16 compact rows x 2 chunks of 32 tokens, 1 KB each
                     const int fr = (q >> 1) * 16 + (lane >> 2), tc = (q & 1) * 32 + (lane & 3) * 8;
-                    if (valid)
-                        *reinterpret_cast<uint4*>(ep.at + blk_off(f0 / 2 + fr, t0 + tc, tok_ld / 32)) = *reinterpret_cast<const uint4*>(ttile + fr * EP + tc * 2);
+                    const uint4 w = *reinterpret_cast<const uint4*>(ttile + fr * EP + tc * 2);
+                    if (FP8 && ep.at_fp8) {     // fp8 weight gradients: the compact transposed survivors leave as codes (a 64-token block = one 64-byte chunk)
+                        if (valid)
+                            *reinterpret_cast<uint2*>(ep.at + blk_off(f0 / 2 + fr, (t0 + tc) / 2, tok_ld / 64)) =
+                                make_uint2(fp8_enc2(bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), ep.inv_out) | (fp8_enc2(bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16), ep.inv_out) << 16),
+                                           fp8_enc2(bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), ep.inv_out) | (fp8_enc2(bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16), ep.inv_out) << 16));
+                    } else if (valid) {
+                        *reinterpret_cast<uint4*>(ep.at + blk_off(f0 / 2 + fr, t0 + tc, tok_ld / 32)) = w;
+                    }
                 }
             }
             wave_lds_sync();

@@ -28,6 +28,66 @@ constexpr int kLoads = 2 + 4 + 1;                // LDS-DMA loads per wavefront 
 
 }  // namespace
 
+// Accumulators of one 128 x 64 wave tile -> bf16 output (one rounding; `alpha` = product of the operand scales of the fp8 form, 1 otherwise).
+template <bool OUT_I_CONTIG>
+__device__ __forceinline__ void wgrad_store(f32x16 (&acc)[4][2], float alpha, unsigned char* smem, int wave, int lane, int i0, int j0, int F, int N,
+                                            uint16_t* __restrict__ out, int64_t ldo) {
+    constexpr int WM = 128, WN = 64, FM = 4, FN = 2;
+    const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, lh = lane >> 5;
+    if (OUT_I_CONTIG) {
+        // out[j * ldo + i]: a lane owns 4 consecutive i of one j; stage [j][i] through LDS (two halves of 64 i)
+        // so that HBM sees 128-byte row segments
+        constexpr int EP = 64 * 2 + 16;
+        unsigned char* scratch = smem + wave * (WN * EP);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int f0 = i0 + wm * WM + h * 64, n0 = j0 + wn * WN;
+#pragma unroll
+            for (int a2 = 0; a2 < 2; ++a2)
+#pragma unroll
+                for (int b = 0; b < FN; ++b)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int a = 2 * h + a2, il = a2 * 32 + 8 * g + 4 * lh;
+                        *reinterpret_cast<uint2*>(scratch + (b * 32 + l32) * EP + il * 2) =
+                            make_uint2(f2bf2(acc[a][b][4 * g] * alpha, acc[a][b][4 * g + 1] * alpha), f2bf2(acc[a][b][4 * g + 2] * alpha, acc[a][b][4 * g + 3] * alpha));
+                    }
+            wave_lds_sync();
+#pragma unroll
+            for (int p = 0; p < WN / 8; ++p) {
+                const int row = p * 8 + (lane >> 3), ch = lane & 7;
+                const int j = n0 + row, i = f0 + ch * 8;
+                if (j < N && i < F)
+                    *reinterpret_cast<uint4*>(out + (int64_t)j * ldo + i) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
+            }
+            wave_lds_sync();
+        }
+    } else {
+        // out[i * ldo + j]: transpose each 32-row slab through LDS for 16-byte row stores
+        constexpr int EP = WN * 2 + 16;
+        unsigned char* scratch = smem + wave * (32 * EP);
+#pragma unroll
+        for (int a = 0; a < FM; ++a) {
+#pragma unroll
+            for (int b = 0; b < FN; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 8 * (r >> 2) + 4 * lh + (r & 3);
+                    *reinterpret_cast<uint16_t*>(scratch + row * EP + (b * 32 + l32) * 2) = (uint16_t)f2bf(acc[a][b][r] * alpha);
+                }
+            wave_lds_sync();
+#pragma unroll
+            for (int p = 0; p < 32 * (WN / 8) / 64; ++p) {
+                const int e = lane + 64 * p, row = e / (WN / 8), ch = e % (WN / 8);
+                const int i = i0 + wm * WM + a * 32 + row, j = j0 + wn * WN + ch * 8;
+                if (i < F && j < N)
+                    *reinterpret_cast<uint4*>(out + (int64_t)i * ldo + j) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
+            }
+            wave_lds_sync();
+        }
+    }
+}
+
 template <bool OUT_I_CONTIG>
 __global__ void __launch_bounds__(512) wgrad_vnm_kernel(const uint16_t* __restrict__ atc, const uint8_t* __restrict__ kmask,
                                                        const uint16_t* __restrict__ G, int F, int N, int Ttot,
@@ -230,58 +290,191 @@ __global__ void __launch_bounds__(512) wgrad_vnm_kernel(const uint16_t* __restri
 #undef SB
     __syncthreads();
 
-    if (OUT_I_CONTIG) {
-        // out[j * ldo + i]: a lane owns 4 consecutive i of one j; stage [j][i] through LDS (two halves of 64 i)
-        // so that HBM sees 128-byte row segments
-        constexpr int EP = 64 * 2 + 16;
-        unsigned char* scratch = smem + wave * (WN * EP);
+    wgrad_store<OUT_I_CONTIG>(acc, 1.0f, smem, wave, lane, i0, j0, F, N, out, ldo);
+}
+
+// The same contraction on E4M3 codes (the fp8 step with SFFN_FLAG_FP8_WGRAD): atc and G hold one code per element, in the blocked layout
+// with a pair of codes per 2-byte element, so one 64-byte chunk of a row is exactly one 64-token block.  v_mfma_scale_f32_32x32x64_f8f6f4 with
+// unit scales contracts one such block per instruction (measured: lane l supplies k 32 (l / 32) .. + 31 of row / column l % 32 in both
+// operands; 2x the bf16 rate).  A stage of the ring is therefore ONE token block: compact A 8 KB + a row of zeros, G 16 KB, 8 private copies
+// of the block's 32 mask bytes; 5 stages; per stage four rows of two matrix instructions, the A fragments read one row ahead, the G
+// fragments one stage ahead.  out = bf16(alpha * sum), alpha = product of the two tensor scales.
+namespace {
+constexpr int k8A = 128 * 64 + 64;               // 128 compact rows x 64 tokens, then one row of zeros
+constexpr int k8B = 256 * 64;
+constexpr int k8Stage = k8A + k8B + 8 * 256;
+constexpr int k8Stages = 5;
+constexpr int k8Loads = 1 + 1 + 2;               // mask, A block, two G blocks per wavefront and stage
+}  // namespace
+
+template <bool OUT_I_CONTIG>
+__global__ void __launch_bounds__(512) wgrad_vnm_fp8_kernel(const uint16_t* __restrict__ atc, const uint8_t* __restrict__ kmask,
+                                                           const uint16_t* __restrict__ G, int F, int N, int Ttot, float alpha,
+                                                           uint16_t* __restrict__ out, int64_t ldo, int tiles_m, int tiles_n) {
+    constexpr int BM = 256, BN = 256, WM = 128, WN = 64, FM = 4, FN = 2;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[k8Stages * k8Stage];
+    static_assert(8 * 64 * (64 * 2 + 16) <= sizeof(smem), "epilogue scratch must fit");
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int l32 = lane & 31, lh = lane >> 5;
+    int L;
+    {
+        const int n = gridDim.x, pid = blockIdx.x, per = n >> 3;
+        L = (pid < per * 8) ? (pid & 7) * per + (pid >> 3) : pid;
+    }
+    int tm, tn;
+    {
+        constexpr int GROUP = SFFN_TILE_GROUP;
+        const int width = GROUP * tiles_n, group = L / width, first = group * GROUP;
+        const int gsz = (tiles_m - first) < GROUP ? (tiles_m - first) : GROUP;
+        tm = first + (L % width) % gsz;
+        tn = (L % width) / gsz;
+    }
+    const int i0 = tm * BM, j0 = tn * BN;
+    const int KC = Ttot / 64;                     // 64-token chunks (64 bytes) per row of the blocked operands
+
+    uint64_t a_base, b_base[2], c_base;
+    const int rb = lane >> 2;
+    const uint32_t blk_lane = (uint32_t)(rb * 32 + ((lane & 3) ^ ((rb >> 2) & 3)) * 8) * 2;   // chunk swizzle, as in the bf16 kernel
+    {
+        int cr = i0 / 2 + wave * 16; cr = cr < F / 2 ? cr : F / 2 - 16;
+        a_base = uniform64(atc + (((int64_t)(cr >> 4) * KC) << 9));
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int f0 = i0 + wm * WM + h * 64, n0 = j0 + wn * WN;
-#pragma unroll
-            for (int a2 = 0; a2 < 2; ++a2)
-#pragma unroll
-                for (int b = 0; b < FN; ++b)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int a = 2 * h + a2, il = a2 * 32 + 8 * g + 4 * lh;
-                        *reinterpret_cast<uint2*>(scratch + (b * 32 + l32) * EP + il * 2) =
-                            make_uint2(f2bf2(acc[a][b][4 * g], acc[a][b][4 * g + 1]), f2bf2(acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]));
-                    }
-            wave_lds_sync();
-#pragma unroll
-            for (int p = 0; p < WN / 8; ++p) {
-                const int row = p * 8 + (lane >> 3), ch = lane & 7;
-                const int j = n0 + row, i = f0 + ch * 8;
-                if (j < N && i < F)
-                    *reinterpret_cast<uint4*>(out + (int64_t)j * ldo + i) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
-            }
-            wave_lds_sync();
+        for (int n = 0; n < 2; ++n) {
+            int gr = j0 + (wave * 2 + n) * 16; gr = gr < N ? gr : N - 16;
+            b_base[n] = uniform64(G + (((int64_t)(gr >> 4) * KC) << 9));
         }
-    } else {
-        // out[i * ldo + j]: transpose each 32-row slab through LDS for 16-byte row stores
-        constexpr int EP = WN * 2 + 16;
-        unsigned char* scratch = smem + wave * (32 * EP);
+        c_base = uniform64(kmask);
+    }
+    uint32_t c_lane;
+    {
+        int g = i0 / 8 + 4 * (lane & 7); g = g < F / 8 ? g : F / 8 - 4;
+        c_lane = (uint32_t)g;
+    }
+    const uint32_t c_kstep = (uint32_t)(F / 8);
+    auto issue = [&](int kt, int stage) {
+        unsigned char* sa = smem + stage * k8Stage;
+        const uint32_t o = blk_lane + (uint32_t)kt * 1024;
+        dma4(c_base, c_lane + (uint32_t)kt * c_kstep, sa + k8A + k8B + wave * 256);     // first: the look-up wants it earliest
+        dma16(a_base, o, sa + wave * 1024);
+        dma16(b_base[0], o, sa + k8A + (wave * 2 + 0) * 1024);
+        dma16(b_base[1], o, sa + k8A + (wave * 2 + 1) * 1024);
+    };
+
+    // fragment reads: a lane wants the 32 bytes k 32 lh .. + 31 of its row = 16-byte chunks 2 lh, 2 lh + 1 (slot = chunk ^ ((row >> 2) & 3))
+    int b_off[FN];
+#pragma unroll
+    for (int b = 0; b < FN; ++b) {
+        const int row = wn * WN + b * 32 + l32;
+        b_off[b] = k8A + row * 64 + (((2 * lh) ^ ((row >> 2) & 3)) << 4);
+    }
+    int a_off[FM], a_next[FM];
+    const uint32_t col = l32 & 7, below = (1u << col) - 1u;
+    const int zero_row = 128 * 64 + (((2 * lh) ^ (l32 >> 3) ^ 2) << 4);
+    uint32_t mk[FM];
+    auto lookup_read = [&](int stage) {
+        const unsigned char* sc = smem + stage * k8Stage + k8A + k8B + wave * 256;
+#pragma unroll
+        for (int a = 0; a < FM; ++a) mk[a] = sc[wm * 16 + a * 4 + (l32 >> 3)];
+    };
+    auto lookup = [&](int stage) {
+        const int sa = stage * k8Stage;
 #pragma unroll
         for (int a = 0; a < FM; ++a) {
-#pragma unroll
-            for (int b = 0; b < FN; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = 8 * (r >> 2) + 4 * lh + (r & 3);
-                    *reinterpret_cast<uint16_t*>(scratch + row * EP + (b * 32 + l32) * 2) = (uint16_t)f2bf(acc[a][b][r]);
-                }
-            wave_lds_sync();
-#pragma unroll
-            for (int p = 0; p < 32 * (WN / 8) / 64; ++p) {
-                const int e = lane + 64 * p, row = e / (WN / 8), ch = e % (WN / 8);
-                const int i = i0 + wm * WM + a * 32 + row, j = j0 + wn * WN + ch * 8;
-                if (i < F && j < N)
-                    *reinterpret_cast<uint4*>(out + (int64_t)i * ldo + j) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
-            }
-            wave_lds_sync();
+            const int gl = wm * 16 + a * 4 + (l32 >> 3);
+            const int row = gl * 4 + __builtin_popcount(mk[a] & below);                   // (row >> 2) & 3 == l32 >> 3
+            a_next[a] = sa + (((mk[a] >> col) & 1u) ? row * 64 + (((2 * lh) ^ (l32 >> 3)) << 4) : zero_row);
         }
+    };
+    auto read_a = [&](Frag16& f, int off) {
+        f.u[0] = *reinterpret_cast<const uint4*>(smem + off);
+        f.u[1] = *reinterpret_cast<const uint4*>(smem + (off ^ 16));
+    };
+    auto read_b = [&](Frag16& f, const unsigned char* st, int b) {
+        f.u[0] = *reinterpret_cast<const uint4*>(st + b_off[b]);
+        f.u[1] = *reinterpret_cast<const uint4*>(st + (b_off[b] ^ 16));
+    };
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int b = 0; b < FN; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
+    auto mma_row = [&](const Frag16& fa, const Frag16 (&fb)[FN], int a) {
+#pragma unroll
+        for (int b = 0; b < FN; ++b)
+            acc[a][b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa.q, fb[b].q, acc[a][b], 0, 0, 0, 0x7F, 0, 0x7F);   // fp8 x fp8, scales 2^0
+    };
+#define SB() __builtin_amdgcn_sched_barrier(0)
+    const int nk = Ttot / 64;
+    {
+        if (tid < k8Stages * 16) *reinterpret_cast<uint32_t*>(smem + (tid >> 4) * k8Stage + 128 * 64 + (tid & 15) * 4) = 0u;   // the rows of zeros
+#pragma unroll
+        for (int p = 0; p < k8Stages; ++p) issue(p < nk ? p : nk - 1, p);
+        wait_vmcnt<(k8Stages - 1) * k8Loads>();
+        __syncthreads();
+        Frag16 A0, A1, B0[FN], B1[FN];
+        lookup_read(0);
+        lookup(0);
+#pragma unroll
+        for (int a = 0; a < FM; ++a) a_off[a] = a_next[a];
+        read_a(A0, a_off[0]);
+#pragma unroll
+        for (int b = 0; b < FN; ++b) read_b(B0[b], smem, b);
+        int stage = 0;
+        // One step = one token block; two steps per loop trip so that the two G fragment sets alternate by name.
+        auto step = [&](int kt, Frag16 (&Bc)[FN], Frag16 (&Bn)[FN]) {
+            const int nxt = (kt + k8Stages < nk) ? kt + k8Stages : nk - 1;
+            const int next_stage = (stage + 1 == k8Stages) ? 0 : stage + 1;
+            const unsigned char* sn = smem + next_stage * k8Stage;
+            read_a(A1, a_off[1]); SB();
+            mma_row(A0, Bc, 0); SB();
+            read_a(A0, a_off[2]); SB();
+            mma_row(A1, Bc, 1); SB();
+            read_a(A1, a_off[3]); SB();
+            // the next block's mask bytes were the first load of its batch
+            wait_vmcnt<(k8Stages - 2) * k8Loads + k8Loads - 1>();
+            lookup_read(next_stage); SB();
+            mma_row(A0, Bc, 2); SB();
+            wait_vmcnt_lgkm0<(k8Stages - 2) * k8Loads>();      // my reads of this stage are done, block kt + 1 has landed (this wavefront's part)
+            __builtin_amdgcn_s_barrier();
+            SB();
+            issue(nxt, stage); SB();
+            lookup(next_stage); SB();
+#pragma unroll
+            for (int a = 0; a < FM; ++a) a_off[a] = a_next[a];
+            read_a(A0, a_off[0]);
+#pragma unroll
+            for (int b = 0; b < FN; ++b) read_b(Bn[b], sn, b);
+            SB();
+            mma_row(A1, Bc, 3); SB();
+            stage = next_stage;
+        };
+        int kt = 0;
+        for (; kt + 1 < nk; kt += 2) { step(kt, B0, B1); step(kt + 1, B1, B0); }
+        if (kt < nk) step(kt, B0, B1);
+        wait_vmcnt<0>();
     }
+#undef SB
+    __syncthreads();
+    wgrad_store<OUT_I_CONTIG>(acc, alpha, smem, wave, lane, i0, j0, F, N, out, ldo);
+}
+
+hipError_t launch_wgrad_vnm_fp8(const uint8_t* atc, const uint8_t* kmask, const uint8_t* Gq, float alpha, int64_t F, int64_t N, int64_t T,
+                                int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
+    if (T % 64 != 0 || T <= 0) return hipErrorInvalidValue;
+    const int tiles_m = (int)((F + 255) / 256), tiles_n = (int)((N + 255) / 256);
+    dim3 grid((unsigned)(tiles_m * tiles_n));
+    const uint16_t* a = reinterpret_cast<const uint16_t*>(atc);
+    const uint16_t* g = reinterpret_cast<const uint16_t*>(Gq);
+    if (out_i_contig)
+        hipLaunchKernelGGL((wgrad_vnm_fp8_kernel<true>), grid, dim3(512), 0, s, a, kmask, g, (int)F, (int)N, (int)T, alpha, out, ldo, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL((wgrad_vnm_fp8_kernel<false>), grid, dim3(512), 0, s, a, kmask, g, (int)F, (int)N, (int)T, alpha, out, ldo, tiles_m, tiles_n);
+    return hipGetLastError();
 }
 
 hipError_t launch_wgrad_vnm(const uint16_t* atc, const uint8_t* kmask, const uint16_t* G, int64_t F, int64_t N, int64_t T,

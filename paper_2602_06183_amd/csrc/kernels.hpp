@@ -39,6 +39,7 @@ struct VnmEpilogue {
     // vals as codes [T, F / 4] and v24 / m24 as a 2:4 code matrix (v24: pairs of codes in the blocked layout, m24: row-major [T, F / 8]);
     // mode 2 keeps vals = dy1 in bf16 and writes v24 as codes.  ykept, at, kmask, colidx, meta stay as in the bf16 modes.
     float inv_out = 1.0f;
+    int at_fp8 = 0;                 // fp8 modes 1 / 2: `at` receives codes (pairs in the blocked layout, [F / 2, T]) instead of bf16
 };
 
 // Grouped (mixture-of-experts) form of a contraction: the token axis is cut into n consecutive segments, one per
@@ -169,6 +170,9 @@ hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R,
 hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
                                    uint8_t* codes_blk, hipStream_t s, uint8_t* src_q_blk = nullptr);
 
+// the same on E4M3 codes (atc: compact transposed codes [F / 2, T], Gq [N, T], both in the blocked pair layout): out = bf16(alpha * sum)
+hipError_t launch_wgrad_vnm_fp8(const uint8_t* atc, const uint8_t* kmask, const uint8_t* Gq, float alpha, int64_t F, int64_t N, int64_t T,
+                                int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
 hipError_t launch_wgrad_vnm(const uint16_t* atc, const uint8_t* kmask, const uint16_t* G, int64_t F, int64_t N, int64_t T,
                             int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 

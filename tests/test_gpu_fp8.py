@@ -171,7 +171,7 @@ def _fp8_step_scales(inp):
                 dy=amax(inp["dY"]) / 448, dy1=max(amax(ref["dy1_vals"]), 1e-6) / 448)
 
 
-def _check_fp8_step_against_oracle(inp, sc, s, outs, mode):
+def _check_fp8_step_against_oracle(inp, sc, s, outs, mode, wgrad_fp8=False):
     """Teacher-forced: every oracle stage consumes the GPU's output of the stage before it."""
     f8 = oracle.fp8
     T, F = s["y1"].shape
@@ -197,26 +197,31 @@ def _check_fp8_step_against_oracle(inp, sc, s, outs, mode):
     assert_gemm_close(s["dy2"], f8.spmm24_fp8(f8.quantize_fp8(inp["dY"], sc["dy"]), sc["dy"], c2, m2, sc["w2"], None), "dy2")
     dv = oracle.dsqrelu_vnm(s["dy2"], s["y1"], ym, cix)
     assert np.array_equal(s["dy1_vals"], dv)
-    assert_gemm_close(outs["dW2"], oracle.vnm_wgrad(yv, ym, cix, inp["dY"], 0), "dW2")
     assert_gemm_close(outs["dX"], f8.vnm_spmm_fp8(f8.quantize_fp8(dv, sc["dy1"]), ym, cix, sc["dy1"], f8.quantize_fp8(inp["W1"], sc["w1"]), sc["w1"], 1), "dX")
-    assert_gemm_close(outs["dW1"], oracle.vnm_wgrad(dv, ym, cix, inp["X"], 1), "dW1")
+    if wgrad_fp8:
+        assert_gemm_close(outs["dW2"], f8.vnm_wgrad_fp8(yc, ym, cix, sc["y2"], f8.quantize_fp8(inp["dY"], sc["dy"]), sc["dy"], 0), "dW2")
+        assert_gemm_close(outs["dW1"], f8.vnm_wgrad_fp8(f8.quantize_fp8(dv, sc["dy1"]), ym, cix, sc["dy1"], xq, sc["x"], 1), "dW1")
+    else:
+        assert_gemm_close(outs["dW2"], oracle.vnm_wgrad(yv, ym, cix, inp["dY"], 0), "dW2")
+        assert_gemm_close(outs["dW1"], oracle.vnm_wgrad(dv, ym, cix, inp["X"], 1), "dW1")
 
 
+@pytest.mark.parametrize("wgrad_fp8", [False, True])
 @pytest.mark.parametrize("T,D,F,mode,seed", [(64, 128, 128, sffn.MODE_HARD, 0), (512, 256, 1024, sffn.MODE_HARD, 0), (512, 256, 1024, sffn.MODE_SOFT, 1),
-                                             (192, 384, 640, sffn.MODE_SOFT, 2)])
-def test_ffn_sparse_step_fp8(T, D, F, mode, seed):
+                                             (192, 384, 640, sffn.MODE_SOFT, 2), (448, 256, 512, sffn.MODE_HARD, 3)])
+def test_ffn_sparse_step_fp8(T, D, F, mode, seed, wgrad_fp8):
     """The fused fp8 step, teacher-forced stage by stage; then the timed configuration (no dense y1 / dy2) must give the same bits."""
     from workload import make_ffn_inputs
     inp = make_ffn_inputs(T, D, F, seed=seed)
     sc = _fp8_step_scales(inp)
     dev = {k: to_dev(v) for k, v in inp.items()}
-    step = sffn.FfnStepFp8(T, D, F, sc, mode, keep_dense=True)
+    step = sffn.FfnStepFp8(T, D, F, sc, mode, keep_dense=True, wgrad_fp8=wgrad_fp8)
     outs = step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
     torch.cuda.synchronize()
     s = {k: to_bits(v) if v.dtype == torch.bfloat16 else v.cpu().numpy() for k, v in step.saved().items()}
     o = {k: to_bits(v) for k, v in zip(("Y3", "dX", "dW1", "dW2"), outs)}
-    _check_fp8_step_against_oracle(inp, sc, s, o, mode)
-    fast = sffn.FfnStepFp8(T, D, F, sc, mode)
+    _check_fp8_step_against_oracle(inp, sc, s, o, mode, wgrad_fp8)
+    fast = sffn.FfnStepFp8(T, D, F, sc, mode, wgrad_fp8=wgrad_fp8)
     outs2 = fast(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
     torch.cuda.synchronize()
     for k, v in zip(("Y3", "dX", "dW1", "dW2"), outs2):
@@ -235,3 +240,23 @@ def test_ffn_sparse_step_fp8_rejects_what_it_does_not_cover():
     z = lambda *shape: torch.zeros(shape, dtype=torch.bfloat16, device="cuda")
     with pytest.raises(sffn.SffnError):
         step(z(64, 128), z(128, 128), z(128, 128), None, z(64, 128))                          # a zero scale
+
+
+def test_fp8_weight_gradient_kernel_exact_on_small_integers():
+    """Pins the operand layout of the dense fp8 matrix instruction and the token-block ring: with integer activations and gradients every
+    product and sum is exact, so eqs. (5), (8) on codes must equal the oracle bit for bit (scales are powers of two)."""
+    rng = np.random.default_rng(2)
+    T, D, F = 448, 128, 256
+    ints = lambda shape, lo, hi: bf16_bits_from_f32(rng.integers(lo, hi, shape).astype(np.float32))
+    inp = dict(X=ints((T, D), -2, 3), W1=ints((F, D), -2, 3), W2=ints((D, F), -2, 3), dY=ints((T, D), -2, 3), b1=np.full(F, -3.0, dtype=np.float32))
+    sc = dict(x=2.0 ** -4, w1=2.0 ** -4, w2=2.0 ** -4, y2=8.0, dy=2.0 ** -4, dy1=64.0)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    step = sffn.FfnStepFp8(T, D, F, sc, keep_dense=True, wgrad_fp8=True)
+    Y3, dX, dW1, dW2 = (to_bits(t) for t in step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"]))
+    ref = oracle.ffn_sparse_step_fp8_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"], sc, wgrad_fp8=True)
+    s = step.saved()
+    assert np.array_equal(to_bits(s["y1"]), ref["y1"])                       # integer sums: eq. (1) is exact on both sides
+    assert np.array_equal(s["y2_codes"].cpu().numpy(), ref["y2_codes"]) and np.array_equal(to_bits(s["dy1_vals"]), ref["dy1_vals"])
+    f32 = oracle.bits_to_f32
+    assert np.array_equal(f32(dW2), f32(ref["dW2"])) and np.array_equal(f32(dW1), f32(ref["dW1"]))
+    assert np.count_nonzero(f32(dW2)) > 1000 and np.count_nonzero(f32(dW1)) > 1000

@@ -329,8 +329,9 @@ def test_full_size_router_step(name, M):
             assert_gemm_close(got, oracle.f64_to_bits(a.T @ oracle.bits_to_f64(G[perm[real]])), "wgrad rows")
 
 
-def test_full_size_fp8_step():
-    """ffn_sparse_step_fp8 at the 1B layer in the timed configuration: packed outputs bit-exact against the oracle's compressors on
+@pytest.mark.parametrize("wgrad_fp8", [False, True])
+def test_full_size_fp8_step(wgrad_fp8):
+    """ffn_sparse_step_fp8 at the 1B layer in the timed configuration (weight gradients in bf16 or on codes): packed outputs bit-exact against the oracle's compressors on
     the kept y1, contractions on sampled rows / columns against the oracle's fp8 contractions (teacher-forced on the GPU's packed operands)."""
     from oracle import fp8 as f8
     T, D, F = CONFIGS["1b"]
@@ -343,7 +344,7 @@ def test_full_size_fp8_step():
     sc = dict(x=amax(dev["X"]) / 448, w1=amax(dev["W1"]) / 448, w2=amax(dev["W2"]) / 448, y2=amax(sv["y2_vals"]) / 448, dy=amax(dev["dY"]) / 448,
               dy1=amax(sv["dy1_vals"]) / 448)
     del ref_step, sv
-    step = sffn.FfnStepFp8(T, D, F, sc)
+    step = sffn.FfnStepFp8(T, D, F, sc, wgrad_fp8=wgrad_fp8)
     Y3, dX, dW1, dW2 = (to_bits(t) for t in step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"]))
     s = {k: (to_bits(v) if v.dtype == torch.bfloat16 else v.cpu().numpy()) for k, v in step.saved().items()}
     c1, m1 = f8.prune24_compress_fp8(inp["W1"], sc["w1"])
@@ -374,6 +375,14 @@ def test_full_size_fp8_step():
     # weight gradients: bf16 contractions over all tokens for sampled hidden units; y2's bf16 survivors are not stored, so eq. (8) only
     cols = np.sort(rng.choice(F // 8, 8, replace=False))[:, None] * 8 + np.arange(8)[None, :]
     cols = cols.reshape(-1)
-    dense_dy1 = oracle.vnm_decompress(s["dy1_vals"], s["y2_meta"], s["colidx"])[:, cols]
-    want = oracle.dense_nt(np.ascontiguousarray(dense_dy1.T), np.ascontiguousarray(inp["X"].T))
-    assert_gemm_close(dW1[cols], want, "dW1")
+    if wgrad_fp8:       # eq. (8) and eq. (5) on codes: dense products of the decoded, decompressed operands, restricted to the sampled hidden units
+        dq = f8.e4m3_decode(oracle.vnm_decompress(f8.quantize_fp8(s["dy1_vals"], sc["dy1"]), s["y2_meta"], s["colidx"])[:, cols]).astype(np.float64)
+        want = dq.T @ f8.e4m3_decode(f8.quantize_fp8(inp["X"], sc["x"])).astype(np.float64) * np.float64(np.float32(sc["dy1"]) * np.float32(sc["x"]))
+        assert_gemm_close(dW1[cols], oracle.f64_to_bits(want), "dW1")
+        yq = f8.e4m3_decode(oracle.vnm_decompress(s["y2_codes"], s["y2_meta"], s["colidx"])[:, cols]).astype(np.float64)
+        want = f8.e4m3_decode(f8.quantize_fp8(inp["dY"], sc["dy"])).astype(np.float64).T @ yq * np.float64(np.float32(sc["y2"]) * np.float32(sc["dy"]))
+        assert_gemm_close(dW2[:, cols], oracle.f64_to_bits(want), "dW2")
+    else:
+        dense_dy1 = oracle.vnm_decompress(s["dy1_vals"], s["y2_meta"], s["colidx"])[:, cols]
+        want = oracle.dense_nt(np.ascontiguousarray(dense_dy1.T), np.ascontiguousarray(inp["X"].T))
+        assert_gemm_close(dW1[cols], want, "dW1")

@@ -244,3 +244,34 @@ def test_fp8_step_saturates_instead_of_overflowing():
     dec = fp8.e4m3_decode(got["xq"])
     assert np.all(np.isfinite(dec)) and np.max(np.abs(dec)) == 448.0 and np.mean(np.abs(dec) == 448.0) > 0.5
     assert np.all(np.isfinite(oracle.bits_to_f32(got["y3"])))
+
+
+def test_fp8_weight_gradients_contract_the_codes_of_the_other_contractions():
+    """wgrad_fp8: eq. (5) / eq. (8) as a plain triple loop over the decoded codes (exact rationals), orientation and scales included;
+    and with every quantised value exactly representable the fp8 weight gradients equal the bf16 ones."""
+    rng = np.random.default_rng(5)
+    T, F, N = 64, 16, 8
+    y1 = bf(rng.integers(-2, 4, (T, F)).astype(np.float32))                                          # y2 in {0, 1, 4, 9}: codes are exact at scale 1/2
+    codes, meta, cix = fp8.sqrelu_vnm_compress_fp8(y1, 0.5)
+    g = bf(rng.integers(-3, 4, (T, N)).astype(np.float32))
+    gq = fp8.quantize_fp8(g, 0.25)
+    dense = oracle.bits_to_f32(oracle.vnm_decompress(fp8.codes_as_bf16_bits(codes), meta, cix)).astype(np.float64)
+    gd = fp8.e4m3_decode(gq).astype(np.float64)
+    for fmaj in (0, 1):
+        got = oracle.bits_to_f32(fp8.vnm_wgrad_fp8(codes, meta, cix, 0.5, gq, 0.25, fmaj))
+        for f in range(F):
+            for n in range(N):
+                want = sum(Fraction(dense[t, f]) * Fraction(gd[t, n]) for t in range(T)) * Fraction(0.5) * Fraction(0.25)
+                assert Fraction(float(got[f, n] if fmaj else got[n, f])) == want          # small integers: the bf16 rounding is exact
+    # all values representable (integers / scale = integers <= 16): the fp8 contraction is the bf16 contraction
+    vals, meta_b, cix_b = oracle.sqrelu_vnm_compress(y1)
+    assert np.array_equal(fp8.vnm_wgrad_fp8(codes, meta, cix, 0.5, gq, 0.25, 1), oracle.vnm_wgrad(vals, meta_b, cix_b, g, 1))
+    inp = _step_inputs(64, 32, 64, seed=9)
+    ref = oracle.ffn_sparse_step_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"])
+    sc = _scales_for(inp, ref)
+    a = oracle.ffn_sparse_step_fp8_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"], sc)
+    b = oracle.ffn_sparse_step_fp8_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"], sc, wgrad_fp8=True)
+    for k in a:                                   # the flag changes the weight gradients and nothing else
+        assert np.array_equal(a[k], b[k]) == (k not in ("dW1", "dW2")), k
+    assert np.array_equal(b["dW2"], fp8.vnm_wgrad_fp8(b["y2_codes"], b["y2_meta"], b["colidx"], sc["y2"], b["dyq"], sc["dy"], 0))
+    assert np.array_equal(b["dW1"], fp8.vnm_wgrad_fp8(b["dy1_codes"], b["y2_meta"], b["colidx"], sc["dy1"], b["xq"], sc["x"], 1))
