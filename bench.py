@@ -67,6 +67,7 @@ def main():
                     help="time the neuron-level router's training step (Section 3.3: ffn_router_full_step = routing + grouped step, M / 4 experts) instead of the magnitude-based V:N:M step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--headline-only", action="store_true", help="skip the other configurations, the stand-alone kernels and the micro-benchmarks (profiling runs)")
+    ap.add_argument("--fp8", action="store_true", help="with --headline-only: also run the fp8 step (both weight-gradient variants) at the headline shape (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference kernel for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -237,6 +238,32 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    def fp8_section(hw, esteps, ewarm, ms16, msd):        # ms16, msd: the bf16-operand sparse step and the dense step of the same run
+        # The same step with fp8 (E4M3) operands in eqs. (1), (3), (4), (7) (Section 3.4, closing paragraph), weight gradients in bf16.
+        # Per-tensor scales as a delayed-scaling recipe would hold them: amax / 448 of each quantised tensor, here from the bf16 step just run.
+        fp8_step = None
+        if not hw.moe and not hw.router and hw.M == 8 and hw.D % 128 == 0 and hw.F % 128 == 0:
+            sv = hw.step.saved()
+            amax = lambda t: max(float(t.float().abs().max()), 1e-12)
+            sc = dict(x=amax(hw.X) / 448, w1=amax(hw.W1) / 448, w2=amax(hw.W2) / 448, y2=amax(sv["y2_vals"]) / 448, dy=amax(hw.dY) / 448,
+                      dy1=amax(sv["dy1_vals"]) / 448)
+            fp8_step = {"workload": hw.name, "bf16_sparse_ms_per_step": round(ms16, 4), "dense_bf16_ms_per_step": round(msd, 4),
+                        "operands": "E4M3 codes in eqs. (1), (3), (4), (7), quantised inside the pruning passes and the V:N:M epilogues; "
+                                    "six per-tensor scales = amax / 448; weight gradients (eqs. (5), (8)) in bf16, or on the same codes (fp8_weight_gradients)"}
+            for name8, w8 in (("bf16_weight_gradients", False), ("fp8_weight_gradients", True)):
+                st8 = sffn.FfnStepFp8(hw.T, hw.D, hw.F, sc, mode, wgrad_fp8=w8)
+                run8 = lambda: st8(hw.X, hw.W1, hw.W2, hw.b1, hw.dY)
+                for _ in range(ewarm):
+                    run8()
+                ms8 = timed(run8, esteps)
+                fp8_step[name8] = {"ms_per_step": round(ms8, 4), "speedup_vs_dense_bf16": round(msd / ms8, 4), "speedup_vs_sparse_bf16": round(ms16 / ms8, 4),
+                                   "tflops_dense_equiv": round(hw.flops / (ms8 * 1e-3) / 1e12, 2)}
+                del st8
+                free()
+            del sv
+            free()
+        return fp8_step
+
     # ================= headline workload ===========================================================================
     M = args.M
     hw = Workload(args.workload, args.zero_fraction, M, args.router)
@@ -310,35 +337,14 @@ def main():
 
     # ================= the other configurations, stand-alone kernels, micro-benchmarks =============================
     configs, kernels, gemm24, venom, router, fp8_bench, wide, router_step, fp8_step = None, None, None, None, None, None, None, None, None
+    if args.headline_only and args.fp8:
+        fp8_step = fp8_section(hw, max(3, min(args.steps, 10)), max(1, min(args.warmup, 2)), res["ms_sparse"], res["ms_dense"])
     if not args.headline_only and not args.router and M == 8:
         esteps, ewarm = max(3, min(args.steps, 10)), max(1, min(args.warmup, 2))
         configs = {}
         key = lambda name, zf: "%s@%.2f" % (name, zf)
         configs[key(hw.name, hw.zf)] = dict(head, headline=True)
-        # The same step with fp8 (E4M3) operands in eqs. (1), (3), (4), (7) (Section 3.4, closing paragraph), weight gradients in bf16.
-        # Per-tensor scales as a delayed-scaling recipe would hold them: amax / 448 of each quantised tensor, here from the bf16 step just run.
-        if not hw.moe and hw.D % 128 == 0 and hw.F % 128 == 0:
-            sv = hw.step.saved()
-            amax = lambda t: max(float(t.float().abs().max()), 1e-12)
-            sc = dict(x=amax(hw.X) / 448, w1=amax(hw.W1) / 448, w2=amax(hw.W2) / 448, y2=amax(sv["y2_vals"]) / 448, dy=amax(hw.dY) / 448,
-                      dy1=amax(sv["dy1_vals"]) / 448)
-            ms16 = timed(hw.sparse_step, esteps)
-            msd = timed(hw.dense_step, esteps)
-            fp8_step = {"workload": hw.name, "bf16_sparse_ms_per_step": round(ms16, 4), "dense_bf16_ms_per_step": round(msd, 4),
-                        "operands": "E4M3 codes in eqs. (1), (3), (4), (7), quantised inside the pruning passes and the V:N:M epilogues; "
-                                    "six per-tensor scales = amax / 448; weight gradients (eqs. (5), (8)) in bf16, or on the same codes (fp8_weight_gradients)"}
-            for name8, w8 in (("bf16_weight_gradients", False), ("fp8_weight_gradients", True)):
-                st8 = sffn.FfnStepFp8(hw.T, hw.D, hw.F, sc, mode, wgrad_fp8=w8)
-                run8 = lambda: st8(hw.X, hw.W1, hw.W2, hw.b1, hw.dY)
-                for _ in range(ewarm):
-                    run8()
-                ms8 = timed(run8, esteps)
-                fp8_step[name8] = {"ms_per_step": round(ms8, 4), "speedup_vs_dense_bf16": round(msd / ms8, 4), "speedup_vs_sparse_bf16": round(ms16 / ms8, 4),
-                                   "tflops_dense_equiv": round(hw.flops / (ms8 * 1e-3) / 1e12, 2)}
-                del st8
-                free()
-            del sv
-            free()
+        fp8_step = fp8_section(hw, esteps, ewarm, res["ms_sparse"], res["ms_dense"])
         # configs[3]'s sweep of the ReLU zero fraction: same tensors, only the bias shifts
         if hw.name == "70b":
             std = neuron_std(hw.host["W1"])

@@ -75,3 +75,13 @@ def test_router_full_step_replays_in_a_graph(M):
     a, b = sffn.FfnRouterStep(T, D, F, M), sffn.FfnRouterStep(T, D, F, M)
     call = lambda step: (lambda d: step.full(d["means"], d["X"], d["W1"], d["W2"], d["b1"], d["dY"]))
     _replay_against_eager(lambda seed: make_router_inputs(T, D, F, M, seed=seed), call(a), call(b), ("means", "X", "W1", "W2", "b1", "dY"))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("wgrad_fp8", [False, True])
+def test_fp8_step_replays_in_a_graph(wgrad_fp8):
+    T, D, F = 256, 256, 512
+    sc = dict(x=4.5 / 448, w1=0.1 / 448, w2=0.1 / 448, y2=2.0 / 448, dy=4.5 / 448, dy1=4.0 / 448)
+    a, b = sffn.FfnStepFp8(T, D, F, sc, wgrad_fp8=wgrad_fp8), sffn.FfnStepFp8(T, D, F, sc, wgrad_fp8=wgrad_fp8)
+    call = lambda step: (lambda d: step(d["X"], d["W1"], d["W2"], d["b1"], d["dY"]))
+    _replay_against_eager(lambda seed: make_ffn_inputs(T, D, F, seed=seed), call(a), call(b), ("X", "W1", "W2", "b1", "dY"))
