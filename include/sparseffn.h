@@ -195,6 +195,8 @@ int vnm_spmm_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* a
  * (8)) are the bf16 contractions on the bf16 survivors.  out = bf16( (sum dec * dec) * (scale_a * scale_b) [+ b1] ).
  * With SFFN_FLAG_FP8_WGRAD the weight gradients also contract codes, the ones the forward / input-gradient contractions already use:
  * dW2 = bf16( (sum_t dec(y2q[t,f]) dec(dYq[t,d])) * (s_y2 s_dy) ), dW1 = bf16( (sum_t dec(dy1q[t,f]) dec(Xq[t,d])) * (s_dy1 s_x) ).
+ * amax (device, 6 floats in the order of the scales, or NULL): the step clears it and leaves the largest magnitude of X, W1, W2, y2's
+ * survivors, dY and dy1's survivors there (exact maxima; what the caller derives the next step's scales from).
  * Shapes: V = 64, M = 8, T a multiple of 64, D and F multiples of 128; cfg->flags: any of SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD.
  * Workspace: sffn_fp8_workspace_bytes(cfg); after the call it holds, at the offsets of sffn_fp8_workspace_layout: the pruned
  * weights (codes [F, D/2] u8 + meta [F, D/8]), y2 (codes [T, F/4] u8, meta [T, F/16], colidx [T/64, F/8, 4]), dy1 at y2's slots
@@ -207,7 +209,7 @@ size_t sffn_fp8_workspace_bytes(const sffn_cfg* cfg);
 int sffn_fp8_workspace_layout(const sffn_cfg* cfg, sffn_fp8_ws_layout* out);
 int ffn_sparse_step_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* scales, const uint16_t* X, const uint16_t* W1,
                         const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
-                        uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
+                        uint16_t* dW2, void* workspace, size_t ws_bytes, float* amax, void* stream);
 
 /* Section 3.3 / Alg. 3 ("Convert Activation to Venom") and the conversion steps 1-3 of Section 3.4: neuron-level
  * experts that produce the V:N:M activation directly.  Reading built here: E = M/4 experts; expert e owns the hidden

@@ -197,6 +197,7 @@ def ffn_sparse_step_fp8_ref(X, W1, W2, b1, dY, scales, mode=HARD, V=64, M=8, wgr
     if wgrad_fp8:
         dW2 = vnm_wgrad_fp8(y2_codes, y2_meta, colidx, s["y2"], dyq, s["dy"], 0, V, M)
         dW1 = vnm_wgrad_fp8(dy1_codes, y2_meta, colidx, s["dy1"], xq, s["x"], 1, V, M)
-    return dict(xq=xq, w1_codes=w1_codes, w1_meta=w1_meta, y1=y1, y2_codes=y2_codes, y2_vals=y2_vals, y2_meta=y2_meta, colidx=colidx,
+    amax_of = dict(x=amax(X), w1=amax(W1), w2=amax(W2), y2=amax(y2_vals), dy=amax(dY), dy1=amax(dy1_vals))     # what the next step's scales come from
+    return dict(amax=amax_of, xq=xq, w1_codes=w1_codes, w1_meta=w1_meta, y1=y1, y2_codes=y2_codes, y2_vals=y2_vals, y2_meta=y2_meta, colidx=colidx,
                 w2q=w2q, y3=y3, dyq=dyq, w2t_codes=w2t_codes, w2t_meta=w2t_meta, dy2=dy2, dW2=dW2, dy1_vals=dy1_vals,
                 dy1_codes=dy1_codes, w1q=w1q, dX=dX, dW1=dW1)

@@ -109,7 +109,7 @@ def load():
     lib.sffn_fp8_workspace_bytes.restype = sz
     lib.sffn_fp8_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg)]
     lib.sffn_fp8_workspace_layout.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Layout)]
-    lib.ffn_sparse_step_fp8.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Scales), p, p, p, p, p, p, p, p, p, p, sz, p]
+    lib.ffn_sparse_step_fp8.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Scales), p, p, p, p, p, p, p, p, p, p, sz, p, p]
     lib.sffn_dense_sqrelu.argtypes = [p, p, i64, p]
     lib.sffn_dense_dsqrelu.argtypes = [p, p, p, i64, p]
     lib.sffn_profile_enable.argtypes = [i32]
@@ -532,6 +532,16 @@ class FfnStepFp8:
         self.ws = _u8((self.layout["total"],), device)
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
         self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
+        self.amax = torch.zeros((8,), dtype=torch.float32, device=device)        # [0:6]: x, w1, w2, y2, dy, dy1 after every call
+
+    def set_scales(self, scales):
+        """New per-tensor scales for the following calls (e.g. amax / 448 of the step before)."""
+        self.scales = _Fp8Scales(*[float(scales[k]) for k in ("x", "w1", "w2", "y2", "dy", "dy1")])
+
+    def amax_dict(self):
+        """The six maxima the last call left on the device (synchronises)."""
+        a = self.amax[:6].tolist()
+        return dict(zip(("x", "w1", "w2", "y2", "dy", "dy1"), a))
 
     def __call__(self, X, W1, W2, b1, dY):
         T, D, F = self.T, self.D, self.F
@@ -541,7 +551,7 @@ class FfnStepFp8:
         _want("ffn_sparse_step_fp8: b1", b1, (F,), _F32, optional=True)
         _want("ffn_sparse_step_fp8: dY", dY, (T, D), _BF16)
         _check(load().ffn_sparse_step_fp8(ctypes.byref(self.cfg), ctypes.byref(self.scales), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY),
-                                          _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _stream()))
+                                          _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _ptr(self.amax), _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
 
     def saved(self):

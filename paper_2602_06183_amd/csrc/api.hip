@@ -382,7 +382,7 @@ int vnm_spmm_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* a
 namespace {
 struct Fp8Layout {
     sffn_fp8_ws_layout pub;
-    size_t w1_blk, w2t_blk, xq, xt_blk, dyq, dyt_blk, w2q, w1tq, v24, m24, at_blk, kmask, total;
+    size_t w1_blk, w2t_blk, xq, xt_blk, dyq, dyt_blk, w2q, w1tq, v24, m24, at_blk, kmask, amax_slots, total;
 };
 bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L) {
     if (!c || !mult64(c->T) || !mult128(c->D) || !mult128(c->F) || c->V != 64 || c->M != 8) return false;
@@ -403,6 +403,7 @@ bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L) {
     L->w2q = take(D * F);                  L->w1tq = take(D * F);
     L->v24 = take(TF / 2);                 L->m24 = take(TF / 8);
     L->at_blk = take(TF);                  L->kmask = take(TF / 64 / 8);
+    L->amax_slots = take((size_t)6 * 64 * 64 * sizeof(float));      // 6 tensors x 64 slots x 256 bytes
     L->total = off;
     L->pub.total = off;
     return true;
@@ -423,8 +424,10 @@ int sffn_fp8_workspace_layout(const sffn_cfg* cfg, sffn_fp8_ws_layout* out) {
 }
 
 int ffn_sparse_step_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* sc, const uint16_t* X, const uint16_t* W1, const uint16_t* W2, const float* b1,
-                        const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
+                        const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, float* amax,
+                        void* stream) {
     REQUIRE(cfg != nullptr && sc != nullptr, SFFN_EINVAL, "ffn_sparse_step_fp8: cfg or scales is null");
+    REQUIRE(aligned16(amax), SFFN_EINVAL, "ffn_sparse_step_fp8: amax must be 16-byte aligned");
     Fp8Layout L;
     REQUIRE(cfg->M == 8 && cfg->V == 64, SFFN_EUNSUPPORTED, "ffn_sparse_step_fp8: only V = 64, M = 8 is built");
     REQUIRE(make_fp8_layout(cfg, &L), SFFN_EINVAL, "ffn_sparse_step_fp8: T must be a positive multiple of 64, D and F of 128; flags: SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD");
@@ -449,36 +452,43 @@ int ffn_sparse_step_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* sc, const ui
     const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
     const bool w8 = (cfg->flags & SFFN_FLAG_FP8_WGRAD) != 0;      // eqs. (5), (8) on codes too: X.T, dY.T and the compact transposed survivors as codes
     const float ix = 1.0f / sc->x, iw1 = 1.0f / sc->w1, iw2 = 1.0f / sc->w2, idy = 1.0f / sc->dy;
+    // amax[0..5] = largest magnitude of x, w1, w2, y2's survivors, dy, dy1's survivors (what next step's scales are made of)
+    // (collected in 64 slots per tensor inside the workspace, folded by the last launch)
+    float* slots = amax ? (float*)(ws + L.amax_slots) : nullptr;
+    auto slot_of = [&](int i) { return slots ? slots + (size_t)i * 64 * 64 : nullptr; };
+    float *ax = slot_of(0), *aw1 = slot_of(1), *aw2 = slot_of(2), *ay2 = slot_of(3), *ady = slot_of(4), *ady1 = slot_of(5);
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
+    if (amax) STAGE(launch_amax_clear(slots, 6, s), "step/clear(amax)");
     // ---- Alg. 1 -------------------------------------------------------------------------------
     if (w8) STAGE(launch_transpose_quantize_fp8_blocked(X, T, D, D, ix, (uint8_t*)xtb, s), "step/quantize(X.T)");     // codes, for eq. (8)
     else    STAGE(launch_transpose(X, T, D, D, xtb, 1, nullptr, s), "step/X.T");                            // bf16, for eq. (8)
-    STAGE(launch_quantize_fp8_blocked(X, T, D, D, ix, xq, s), "step/quantize(X)");
+    STAGE(launch_quantize_fp8_blocked(X, T, D, D, ix, xq, s, ax), "step/quantize(X)");
     STAGE(launch_prune24_fp8_step(W1, F, D, D, 0, cfg->mode, iw1, w1c, w1m, w1b, s), "step/prune24_fp8(W1)");
     {   // eq. (1) on codes, then eq. (2) + V:N:M compression on the bf16 tile; the survivors leave as codes (and in bf16 for eq. (5))
         VnmEpilogue ep;
         ep.mode = 1; ep.store_dense = keep_dense; ep.vals = (uint16_t*)y2c; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
-        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->y2; ep.at_fp8 = w8;
+        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->y2; ep.at_fp8 = w8; ep.amax = ay2;
         STAGE(launch_gemm_fp8_blocked(w1b, w1m, xq, b1, sc->x * sc->w1, F, T, D, y1, F, &ep, s), "step/y1+sqrelu_vnm_compress");
     }
-    STAGE(launch_prune24_fp8_step(W2, F, D, F, 1, cfg->mode, iw2, w2c, w2m, w2b, s, w2q), "step/prune24_fp8(W2.T)+quantize(W2)");
+    STAGE(launch_prune24_fp8_step(W2, F, D, F, 1, cfg->mode, iw2, w2c, w2m, w2b, s, w2q, aw2), "step/prune24_fp8(W2.T)+quantize(W2)");
     STAGE(launch_gemm_fp8_blocked(v24, m24, w2q, nullptr, sc->y2 * sc->w2, T, D, F, Y3, D, nullptr, s), "step/y3");      // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
     if (w8) STAGE(launch_transpose_quantize_fp8_blocked(dY, T, D, D, idy, (uint8_t*)dytb, s), "step/quantize(dY.T)");
     else    STAGE(launch_transpose(dY, T, D, D, dytb, 1, nullptr, s), "step/dY.T");                         // bf16, for eq. (5)
-    STAGE(launch_quantize_fp8_blocked(dY, T, D, D, idy, dyq, s), "step/quantize(dY)");
+    STAGE(launch_quantize_fp8_blocked(dY, T, D, D, idy, dyq, s, ady), "step/quantize(dY)");
     if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)dytb, sc->y2 * sc->dy, F, D, T, 1, dW2, F, s), "step/dW2");   // eq. (5) on codes
     else    STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, nullptr), "step/dW2");          // eq. (5), bf16
     {   // eq. (4) on codes, then eq. (6) in bf16 on y2's kept slots; dy1 leaves in bf16 (canonical, eq. (8)) and as codes (eq. (7))
         VnmEpilogue ep;
         ep.mode = 2; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
-        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->dy1; ep.at_fp8 = w8;
+        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->dy1; ep.at_fp8 = w8; ep.amax = ady1;
         STAGE(launch_gemm_fp8_blocked(w2b, w2m, dyq, nullptr, sc->dy * sc->w2, F, T, D, dy2, F, &ep, s), "step/dy2+dsqrelu_vnm");
     }
-    STAGE(launch_transpose_quantize_fp8_blocked(W1, F, D, D, iw1, w1tq, s), "step/quantize(W1.T)");
+    STAGE(launch_transpose_quantize_fp8_blocked(W1, F, D, D, iw1, w1tq, s, aw1), "step/quantize(W1.T)");
     STAGE(launch_gemm_fp8_blocked(v24, m24, w1tq, nullptr, sc->dy1 * sc->w1, T, D, F, dX, D, nullptr, s), "step/dX");      // eq. (7)
     if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)xtb, sc->dy1 * sc->x, F, D, T, 0, dW1, D, s), "step/dW1");   // eq. (8) on codes
     else    STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, nullptr), "step/dW1");           // eq. (8), bf16
+    if (amax) STAGE(launch_amax_finish(slots, 6, amax, s), "step/finish(amax)");
     return SFFN_OK;
 }
 

@@ -32,6 +32,27 @@ __device__ __forceinline__ uint32_t fp8_enc2(float a, float b, float inv) {
     return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(ma, mb, 0, false) & 0xFFFFu;
 }
 
+// Largest magnitude seen by a wavefront -> *amax (device float32, atomic max on the bit pattern: non-negative floats order like their bits).
+// m >= 0; every lane of the wavefront must call it.  At most one atomic per wavefront, and none when the value already there is
+// at least as large (tens of thousands of wavefronts hitting one address serialise in L2: 1.5 ms instead of 0.03 for a pass over
+// 128 MB; a stale read only costs a redundant atomic).
+__device__ __forceinline__ void note_amax(float* amax, float m) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) m = __builtin_fmaxf(m, __shfl_xor(m, o, 64));
+    if (amax && (threadIdx.x & 63) == 0) {
+        unsigned int* p = reinterpret_cast<unsigned int*>(amax);
+        if (__float_as_uint(m) > __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(p, __float_as_uint(m));
+    }
+}
+
+// The same for the kernels of the fused fp8 step: 64 slots per tensor, 256 bytes apart (slot = workgroup id % 64), so that the reads and
+// atomics of a launch spread over cache lines and L2 channels; amax_finish_kernel (fp8.hip) folds the slots at the end of the step.
+constexpr int kAmaxSlots = 64, kAmaxSlotStride = 64;      // floats
+__device__ __forceinline__ void note_amax_slots(float* slots, float m) {
+    if (slots) note_amax(slots + (((blockIdx.y * gridDim.x + blockIdx.x) & (kAmaxSlots - 1)) * kAmaxSlotStride), m);
+    else note_amax(nullptr, m);
+}
+
 // 2:4 selection on one group of four bf16 (a0..a3 as 16-bit patterns): rank by magnitude
 // descending, index ascending; the two first survive (Section 2.2 of the paper, with the tie rule
 // of the packed-format contract).  Returns v0 | v1 << 16 (survivors in ascending position) and

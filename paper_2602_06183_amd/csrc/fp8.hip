@@ -20,12 +20,6 @@ namespace {
 
 __device__ __forceinline__ uint32_t enc2(float a, float b, float inv) { return fp8_enc2(a, b, inv); }
 
-__device__ __forceinline__ void note_amax(float* amax, float m) {      // m >= 0; one atomic per wavefront
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) m = __builtin_fmaxf(m, __shfl_xor(m, o, 64));
-    if (amax && (threadIdx.x & 63) == 0) atomicMax(reinterpret_cast<unsigned int*>(amax), __float_as_uint(m));
-}
-
 // 2:4 selection as select24 (common.hpp) but returning the survivors as float32 reals: bit copies widened (HARD) or
 // a -/+ t evaluated in float32 (SOFT), not rounded to bf16.
 template <bool SOFT>
@@ -88,22 +82,27 @@ __global__ void __launch_bounds__(256) prune24_rows_fp8_kernel(const uint16_t* _
 template <bool SOFT>
 __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* __restrict__ src, int64_t R, int K, int64_t ld, float inv,
                                                               uint8_t* __restrict__ codes, uint8_t* __restrict__ meta, float* __restrict__ amax,
-                                                              uint16_t* __restrict__ codes_blk, uint16_t* __restrict__ src_q_blk) {
+                                                              uint16_t* __restrict__ codes_blk, uint16_t* __restrict__ src_q_blk, float* __restrict__ amax_src) {
     constexpr int TK = 128, TR = 64, PITCH = TR + 8;
     __shared__ __attribute__((aligned(16))) uint16_t tile[TK * PITCH];
     const int64_t r0 = (int64_t)blockIdx.x * TR;
     const int k0 = blockIdx.y * TK;
     const int tid = threadIdx.x;
+    float m_src = 0.0f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int kk = tid / 8 + 32 * i, seg = tid % 8;
         uint4 w = make_uint4(0, 0, 0, 0);
         if (k0 + kk < K) w = *reinterpret_cast<const uint4*>(src + (int64_t)(k0 + kk) * ld + r0 + seg * 8);
         *reinterpret_cast<uint4*>(&tile[kk * PITCH + seg * 8]) = w;
-        if (src_q_blk && k0 + kk < K)      // the unpruned source itself, quantised, in its own orientation [K rows, R codes] (blocked pairs)
+        if (src_q_blk && k0 + kk < K) {    // the unpruned source itself, quantised, in its own orientation [K rows, R codes] (blocked pairs)
+            const float f[8] = {bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16),
+                                bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16)};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) m_src = __builtin_fmaxf(m_src, __builtin_fabsf(f[e]));
             *reinterpret_cast<uint2*>(src_q_blk + blk_off(k0 + kk, (r0 + seg * 8) / 2, R / 64)) =
-                make_uint2(enc2(bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), inv) | (enc2(bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16), inv) << 16),
-                           enc2(bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), inv) | (enc2(bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16), inv) << 16));
+                make_uint2(enc2(f[0], f[1], inv) | (enc2(f[2], f[3], inv) << 16), enc2(f[4], f[5], inv) | (enc2(f[6], f[7], inv) << 16));
+        }
     }
     __syncthreads();
     const int rr = tid % 64, q = tid / 64;
@@ -127,6 +126,7 @@ __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* _
         if (codes_blk) *reinterpret_cast<uint4*>(codes_blk + blk_off(r, (k0 + 32 * q) / 4, K / 128)) = make_uint4(oc[0], oc[1], oc[2], oc[3]);   // 16 codes = 8 pairs
     }
     note_amax(amax, m);
+    if (amax_src) note_amax_slots(amax_src, m_src);      // over every element of the source (its dense use shares the scale)
 }
 
 // eq. (2) + V:N:M compression with fp8 values: the structure of sqrelu_vnm_compress_m_kernel (vnm_general.hip): one workgroup =
@@ -254,20 +254,26 @@ __global__ void __launch_bounds__(256) transpose_u8_kernel(const uint8_t* __rest
 
 // [R, C] bf16 (row stride ld) -> codes in the blocked pair layout, same orientation: one thread per 8 elements
 __global__ void __launch_bounds__(256) quantize_fp8_blocked_kernel(const uint16_t* __restrict__ src, int64_t R, int C8, int64_t ld, float inv,
-                                                                  uint16_t* __restrict__ out) {
+                                                                  uint16_t* __restrict__ out, float* __restrict__ amax) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= R * C8) return;
-    const int64_t r = i / C8;
-    const int c = (int)(i - r * C8) * 8;
-    const uint4 w = *reinterpret_cast<const uint4*>(src + r * ld + c);
-    *reinterpret_cast<uint2*>(out + blk_off(r, c / 2, C8 / 8)) =
-        make_uint2(enc2(bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), inv) | (enc2(bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16), inv) << 16),
-                   enc2(bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), inv) | (enc2(bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16), inv) << 16));
+    float m = 0.0f;
+    if (i < R * C8) {
+        const int64_t r = i / C8;
+        const int c = (int)(i - r * C8) * 8;
+        const uint4 w = *reinterpret_cast<const uint4*>(src + r * ld + c);
+        const float f[8] = {bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16),
+                            bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16)};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) m = __builtin_fmaxf(m, __builtin_fabsf(f[e]));
+        *reinterpret_cast<uint2*>(out + blk_off(r, c / 2, C8 / 8)) =
+            make_uint2(enc2(f[0], f[1], inv) | (enc2(f[2], f[3], inv) << 16), enc2(f[4], f[5], inv) | (enc2(f[6], f[7], inv) << 16));
+    }
+    note_amax_slots(amax, m);
 }
 
 // [R, C] bf16 -> codes of the transposed matrix [C, R] in the blocked pair layout; 64 x 64 tiles through LDS
 __global__ void __launch_bounds__(256) transpose_quantize_fp8_blocked_kernel(const uint16_t* __restrict__ src, int64_t R, int64_t C, int64_t ld, float inv,
-                                                                            uint16_t* __restrict__ out) {
+                                                                            uint16_t* __restrict__ out, float* __restrict__ amax) {
     __shared__ uint16_t tile[64][64 + 2];
     const int tid = threadIdx.x;
     const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
@@ -279,27 +285,51 @@ __global__ void __launch_bounds__(256) transpose_quantize_fp8_blocked_kernel(con
         d[0] = w.x; d[1] = w.y; d[2] = w.z; d[3] = w.w;
     }
     __syncthreads();
+    float m = 0.0f;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int c = tid / 8 + 32 * i, rs = (tid % 8) * 8;          // output row c0 + c, its 8 codes for source rows r0 + rs .. + 7
         uint32_t q[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) q[j] = enc2(bf2f(tile[rs + 2 * j][c]), bf2f(tile[rs + 2 * j + 1][c]), inv);
+        for (int j = 0; j < 4; ++j) {
+            const float lo = bf2f(tile[rs + 2 * j][c]), hi = bf2f(tile[rs + 2 * j + 1][c]);
+            m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(lo), __builtin_fabsf(hi)));
+            q[j] = enc2(lo, hi, inv);
+        }
         *reinterpret_cast<uint2*>(out + blk_off(c0 + c, (r0 + rs) / 2, R / 64)) = make_uint2(q[0] | (q[1] << 16), q[2] | (q[3] << 16));
     }
+    note_amax_slots(amax, m);
 }
 
-hipError_t launch_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_blk, hipStream_t s) {
+hipError_t launch_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_blk, hipStream_t s, float* amax) {
     if (C % 64 != 0 || R % 16 != 0) return hipErrorInvalidValue;
     const int64_t n = R * (C / 8);
-    hipLaunchKernelGGL(quantize_fp8_blocked_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, R, (int)(C / 8), ld, inv, reinterpret_cast<uint16_t*>(out_blk));
+    hipLaunchKernelGGL(quantize_fp8_blocked_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, R, (int)(C / 8), ld, inv, reinterpret_cast<uint16_t*>(out_blk), amax);
     return hipGetLastError();
 }
 
-hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s) {
+// The amax slots of the fused fp8 step (common.hpp): n tensors x 64 slots.  clear: before the first kernel (a kernel, not a memset node:
+// the step may be captured in a graph); finish: out[i] = max over tensor i's slots.
+__global__ void amax_clear_kernel(float* slots) { slots[(blockIdx.x * kAmaxSlots + threadIdx.x) * kAmaxSlotStride] = 0.0f; }
+__global__ void amax_finish_kernel(const float* slots, float* out) {
+    float m = slots[(blockIdx.x * kAmaxSlots + threadIdx.x) * kAmaxSlotStride];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) m = __builtin_fmaxf(m, __shfl_xor(m, o, 64));
+    if (threadIdx.x == 0) out[blockIdx.x] = m;
+}
+hipError_t launch_amax_clear(float* slots, int n, hipStream_t s) {
+    hipLaunchKernelGGL(amax_clear_kernel, dim3(n), dim3(kAmaxSlots), 0, s, slots);
+    return hipGetLastError();
+}
+hipError_t launch_amax_finish(const float* slots, int n, float* out, hipStream_t s) {
+    hipLaunchKernelGGL(amax_finish_kernel, dim3(n), dim3(kAmaxSlots), 0, s, slots, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s, float* amax) {
     if (C % 64 != 0 || R % 64 != 0) return hipErrorInvalidValue;
     hipLaunchKernelGGL(transpose_quantize_fp8_blocked_kernel, dim3((unsigned)(C / 64), (unsigned)(R / 64)), dim3(256), 0, s, src, R, C, ld, inv,
-                       reinterpret_cast<uint16_t*>(out_t_blk));
+                       reinterpret_cast<uint16_t*>(out_t_blk), amax);
     return hipGetLastError();
 }
 
@@ -310,22 +340,22 @@ hipError_t launch_quantize_fp8(const uint16_t* src, int64_t n, float inv, uint8_
 }
 
 static hipError_t launch_prune24_fp8_impl(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                          float* amax, uint16_t* blk, uint16_t* srcq, hipStream_t s);
+                                          float* amax, uint16_t* blk, uint16_t* srcq, float* amax_src, hipStream_t s);
 
 hipError_t launch_prune24_fp8(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
                               float* amax, hipStream_t s) {
-    return launch_prune24_fp8_impl(src, R, K, ld, trans, mode, inv, codes, meta, amax, nullptr, nullptr, s);
+    return launch_prune24_fp8_impl(src, R, K, ld, trans, mode, inv, codes, meta, amax, nullptr, nullptr, nullptr, s);
 }
 
 hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                   uint8_t* codes_blk, hipStream_t s, uint8_t* src_q_blk) {
+                                   uint8_t* codes_blk, hipStream_t s, uint8_t* src_q_blk, float* amax_src) {
     if (K % 128 != 0 || (src_q_blk && (!trans || R % 64 != 0 || K % 16 != 0))) return hipErrorInvalidValue;   // a block row holds whole 64-byte pieces of the K / 2 codes per row
     return launch_prune24_fp8_impl(src, R, K, ld, trans, mode, inv, codes, meta, nullptr, reinterpret_cast<uint16_t*>(codes_blk),
-                                   reinterpret_cast<uint16_t*>(src_q_blk), s);
+                                   reinterpret_cast<uint16_t*>(src_q_blk), src_q_blk ? amax_src : nullptr, s);
 }
 
 static hipError_t launch_prune24_fp8_impl(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                          float* amax, uint16_t* blk, uint16_t* srcq, hipStream_t s) {
+                                          float* amax, uint16_t* blk, uint16_t* srcq, float* amax_src, hipStream_t s) {
     if (!trans) {
         const int64_t nchunks = R * (K / 8);
         const unsigned grid = (unsigned)((nchunks + 255) / 256);
@@ -333,8 +363,8 @@ static hipError_t launch_prune24_fp8_impl(const uint16_t* src, int64_t R, int64_
         else           hipLaunchKernelGGL((prune24_rows_fp8_kernel<true>), dim3(grid), dim3(256), 0, s, src, nchunks, (int)(K / 8), ld, inv, codes, meta, amax, blk);
     } else {
         dim3 grid((unsigned)(R / 64), (unsigned)((K + 127) / 128));
-        if (mode == 0) hipLaunchKernelGGL((prune24_cols_fp8_kernel<false>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq);
-        else           hipLaunchKernelGGL((prune24_cols_fp8_kernel<true>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq);
+        if (mode == 0) hipLaunchKernelGGL((prune24_cols_fp8_kernel<false>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq, amax_src);
+        else           hipLaunchKernelGGL((prune24_cols_fp8_kernel<true>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq, amax_src);
     }
     return hipGetLastError();
 }

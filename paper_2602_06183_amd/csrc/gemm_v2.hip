@@ -614,6 +614,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         pre_y[it] = kept_p[it * 64];
                     }
                 }
+                float vmax = 0.0f;                                         // fp8: largest survivor magnitude of this half tile
                 if (valid) {
 #pragma unroll
                     for (int it = 0; it < 8; ++it) {
@@ -651,6 +652,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             v = f2bf2(ga, gb);
                             vals_p[(int64_t)it * 8 * (F / 8)] = v;
                         }
+                        if (FP8) vmax = __builtin_fmaxf(vmax, __builtin_fmaxf(__builtin_fabsf(bf2f(v & 0xFFFFu)), __builtin_fabsf(bf2f(v >> 16))));
                         // the same block as two plain 2:4 groups (blocked operand of eq. (3) / eq. (7))
                         if (ep.v24) {       // (not wanted when eq. (7) gathers rows from the canonical arrays)
                             uint32_t a24, b24, mb8;
@@ -674,6 +676,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         *reinterpret_cast<uint16_t*>(ttile + (bl * 4 + (nib >> 2)) * EP + t * 2) = (uint16_t)(v >> 16);
                     }
                 }
+                if (FP8 && ep.amax) note_amax_slots(ep.amax, vmax);
                 wave_lds_sync();
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {          // 2 groups of 16 compact rows x 2 chunks of 32 tokens, 1 KB each

@@ -40,6 +40,7 @@ struct VnmEpilogue {
     // mode 2 keeps vals = dy1 in bf16 and writes v24 as codes.  ykept, at, kmask, colidx, meta stay as in the bf16 modes.
     float inv_out = 1.0f;
     int at_fp8 = 0;                 // fp8 modes 1 / 2: `at` receives codes (pairs in the blocked layout, [F / 2, T]) instead of bf16
+    float* amax = nullptr;          // fp8 modes 1 / 2: amax slots for the survivors' magnitudes (y2 / dy1)
 };
 
 // Grouped (mixture-of-experts) form of a contraction: the token axis is cut into n consecutive segments, one per
@@ -164,11 +165,16 @@ hipError_t launch_spmm24_fp8(const uint8_t* a_codes, const uint8_t* a_meta, cons
 hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* Bq, const float* bias, float alpha, int64_t Ra,
                                    int64_t Rb, int64_t K, uint16_t* out, int64_t ldo, const VnmEpilogue* ep, hipStream_t s);
 // fp8.hip, producers of such operands: quantised copy in the same orientation / transposed; 2:4 pruning that also writes the blocked codes
-hipError_t launch_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_blk, hipStream_t s);
-hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s);
+// (amax, optional: the tensor's amax slots, see below)
+hipError_t launch_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_blk, hipStream_t s, float* amax = nullptr);
+hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s,
+                                                 float* amax = nullptr);
+// amax slots of the fused fp8 step: n tensors x 64 slots x 256 bytes (kAmaxSlots, kAmaxSlotStride in common.hpp); the step's kernels take a tensor's slot base
+hipError_t launch_amax_clear(float* slots, int n, hipStream_t s);
+hipError_t launch_amax_finish(const float* slots, int n, float* out, hipStream_t s);
 // (src_q_blk, trans = 1 only: also the unpruned source quantised in its own orientation, [K rows, R codes])
 hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                   uint8_t* codes_blk, hipStream_t s, uint8_t* src_q_blk = nullptr);
+                                   uint8_t* codes_blk, hipStream_t s, uint8_t* src_q_blk = nullptr, float* amax_src = nullptr);
 
 // the same on E4M3 codes (atc: compact transposed codes [F / 2, T], Gq [N, T], both in the blocked pair layout): out = bf16(alpha * sum)
 hipError_t launch_wgrad_vnm_fp8(const uint8_t* atc, const uint8_t* kmask, const uint8_t* Gq, float alpha, int64_t F, int64_t N, int64_t T,

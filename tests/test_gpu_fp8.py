@@ -221,11 +221,19 @@ def test_ffn_sparse_step_fp8(T, D, F, mode, seed, wgrad_fp8):
     s = {k: to_bits(v) if v.dtype == torch.bfloat16 else v.cpu().numpy() for k, v in step.saved().items()}
     o = {k: to_bits(v) for k, v in zip(("Y3", "dX", "dW1", "dW2"), outs)}
     _check_fp8_step_against_oracle(inp, sc, s, o, mode, wgrad_fp8)
+    # the six maxima for the next step's scales: exact, whatever order the atomics arrive in
+    yv = oracle.sqrelu_vnm_compress(s["y1"])[0]
+    amax = lambda b: float(np.float32(np.abs(oracle.bits_to_f32(b)).max()))
+    want = dict(x=amax(inp["X"]), w1=amax(inp["W1"]), w2=amax(inp["W2"]), y2=amax(yv), dy=amax(inp["dY"]), dy1=amax(s["dy1_vals"]))
+    assert step.amax_dict() == want
     fast = sffn.FfnStepFp8(T, D, F, sc, mode, wgrad_fp8=wgrad_fp8)
     outs2 = fast(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
     torch.cuda.synchronize()
     for k, v in zip(("Y3", "dX", "dW1", "dW2"), outs2):
         assert np.array_equal(to_bits(v), o[k]), k
+    assert fast.amax_dict() == want
+    fast(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])            # a second call clears the maxima first
+    assert fast.amax_dict() == want
     s2 = fast.saved()
     for k in ("y2_codes", "y2_meta", "colidx", "w1_codes", "w2t_codes"):
         assert np.array_equal(s2[k].cpu().numpy(), s[k]), k
@@ -260,3 +268,22 @@ def test_fp8_weight_gradient_kernel_exact_on_small_integers():
     f32 = oracle.bits_to_f32
     assert np.array_equal(f32(dW2), f32(ref["dW2"])) and np.array_equal(f32(dW1), f32(ref["dW1"]))
     assert np.count_nonzero(f32(dW2)) > 1000 and np.count_nonzero(f32(dW1)) > 1000
+
+
+def test_fp8_step_delayed_scaling_round_trip():
+    """The maxima one call leaves behind, turned into the next call's scales (amax / 448), put every tensor's largest code at the
+    top of the E4M3 range without saturating anything else - the loop a delayed-scaling recipe runs."""
+    T, D, F = 256, 256, 512
+    inp = make_ffn_inputs(T, D, F, seed=4)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    step = sffn.FfnStepFp8(T, D, F, dict(x=1.0, w1=1.0, w2=1.0, y2=1.0, dy=1.0, dy1=1.0))      # first call: scales unknown
+    step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    a = step.amax_dict()
+    assert all(v > 0 for v in a.values())
+    step.set_scales({k: v / 448.0 for k, v in a.items()})
+    step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    s = step.saved()
+    for name in ("w1_codes", "w2t_codes", "y2_codes"):
+        top = np.abs(fp8.e4m3_decode(s[name].cpu().numpy())).max()
+        assert 416.0 <= top <= 448.0, (name, top)              # the largest survivor lands in the top binade (exactly 448 when it is the tensor's maximum)
+    assert np.abs(fp8.e4m3_decode(s["y2_codes"].cpu().numpy())).max() == 448.0

@@ -272,6 +272,9 @@ def test_fp8_weight_gradients_contract_the_codes_of_the_other_contractions():
     a = oracle.ffn_sparse_step_fp8_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"], sc)
     b = oracle.ffn_sparse_step_fp8_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"], sc, wgrad_fp8=True)
     for k in a:                                   # the flag changes the weight gradients and nothing else
-        assert np.array_equal(a[k], b[k]) == (k not in ("dW1", "dW2")), k
+        if k != "amax":
+            assert np.array_equal(a[k], b[k]) == (k not in ("dW1", "dW2")), k
+    assert a["amax"] == b["amax"] and a["amax"]["x"] == np.float32(np.abs(oracle.bits_to_f32(inp["X"])).max()) \
+        and a["amax"]["y2"] == np.float32(oracle.bits_to_f32(a["y2_vals"]).max()) and a["amax"]["dy1"] == np.float32(np.abs(oracle.bits_to_f32(a["dy1_vals"])).max())
     assert np.array_equal(b["dW2"], fp8.vnm_wgrad_fp8(b["y2_codes"], b["y2_meta"], b["colidx"], sc["y2"], b["dyq"], sc["dy"], 0))
     assert np.array_equal(b["dW1"], fp8.vnm_wgrad_fp8(b["dy1_codes"], b["y2_meta"], b["colidx"], sc["dy1"], b["xq"], sc["x"], 1))
