@@ -460,10 +460,14 @@ int ffn_sparse_step_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* sc, const ui
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
     if (amax) STAGE(launch_amax_clear(slots, 6, s), "step/clear(amax)");
     // ---- Alg. 1 -------------------------------------------------------------------------------
-    if (w8) STAGE(launch_transpose_quantize_fp8_blocked(X, T, D, D, ix, (uint8_t*)xtb, s), "step/quantize(X.T)");     // codes, for eq. (8)
-    else    STAGE(launch_transpose(X, T, D, D, xtb, 1, nullptr, s), "step/X.T");                            // bf16, for eq. (8)
-    STAGE(launch_quantize_fp8_blocked(X, T, D, D, ix, xq, s, ax), "step/quantize(X)");
-    STAGE(launch_prune24_fp8_step(W1, F, D, D, 0, cfg->mode, iw1, w1c, w1m, w1b, s), "step/prune24_fp8(W1)");
+    if (w8) {       // X.T codes for eq. (8) and X codes for eq. (1) in one pass over X
+        STAGE(launch_transpose_quantize_fp8_blocked(X, T, D, D, ix, (uint8_t*)xtb, s, ax, xq), "step/quantize(X, X.T)");
+    } else {
+        STAGE(launch_transpose(X, T, D, D, xtb, 1, nullptr, s), "step/X.T");                                // bf16, for eq. (8)
+        STAGE(launch_quantize_fp8_blocked(X, T, D, D, ix, xq, s, ax), "step/quantize(X)");
+    }
+    // W1 in one pass: pruned (canonical + blocked codes) for eq. (1), dense and transposed for eq. (7)
+    STAGE(launch_transpose_quantize_fp8_blocked(W1, F, D, D, iw1, w1tq, s, aw1, nullptr, cfg->mode, w1c, w1m, w1b), "step/prune24_fp8(W1)+quantize(W1.T)");
     {   // eq. (1) on codes, then eq. (2) + V:N:M compression on the bf16 tile; the survivors leave as codes (and in bf16 for eq. (5))
         VnmEpilogue ep;
         ep.mode = 1; ep.store_dense = keep_dense; ep.vals = (uint16_t*)y2c; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
@@ -473,9 +477,12 @@ int ffn_sparse_step_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* sc, const ui
     STAGE(launch_prune24_fp8_step(W2, F, D, F, 1, cfg->mode, iw2, w2c, w2m, w2b, s, w2q, aw2), "step/prune24_fp8(W2.T)+quantize(W2)");
     STAGE(launch_gemm_fp8_blocked(v24, m24, w2q, nullptr, sc->y2 * sc->w2, T, D, F, Y3, D, nullptr, s), "step/y3");      // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
-    if (w8) STAGE(launch_transpose_quantize_fp8_blocked(dY, T, D, D, idy, (uint8_t*)dytb, s), "step/quantize(dY.T)");
-    else    STAGE(launch_transpose(dY, T, D, D, dytb, 1, nullptr, s), "step/dY.T");                         // bf16, for eq. (5)
-    STAGE(launch_quantize_fp8_blocked(dY, T, D, D, idy, dyq, s, ady), "step/quantize(dY)");
+    if (w8) {
+        STAGE(launch_transpose_quantize_fp8_blocked(dY, T, D, D, idy, (uint8_t*)dytb, s, ady, dyq), "step/quantize(dY, dY.T)");
+    } else {
+        STAGE(launch_transpose(dY, T, D, D, dytb, 1, nullptr, s), "step/dY.T");                             // bf16, for eq. (5)
+        STAGE(launch_quantize_fp8_blocked(dY, T, D, D, idy, dyq, s, ady), "step/quantize(dY)");
+    }
     if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)dytb, sc->y2 * sc->dy, F, D, T, 1, dW2, F, s), "step/dW2");   // eq. (5) on codes
     else    STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, nullptr), "step/dW2");          // eq. (5), bf16
     {   // eq. (4) on codes, then eq. (6) in bf16 on y2's kept slots; dy1 leaves in bf16 (canonical, eq. (8)) and as codes (eq. (7))
@@ -484,7 +491,6 @@ int ffn_sparse_step_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* sc, const ui
         ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->dy1; ep.at_fp8 = w8; ep.amax = ady1;
         STAGE(launch_gemm_fp8_blocked(w2b, w2m, dyq, nullptr, sc->dy * sc->w2, F, T, D, dy2, F, &ep, s), "step/dy2+dsqrelu_vnm");
     }
-    STAGE(launch_transpose_quantize_fp8_blocked(W1, F, D, D, iw1, w1tq, s, aw1), "step/quantize(W1.T)");
     STAGE(launch_gemm_fp8_blocked(v24, m24, w1tq, nullptr, sc->dy1 * sc->w1, T, D, F, dX, D, nullptr, s), "step/dX");      // eq. (7)
     if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)xtb, sc->dy1 * sc->x, F, D, T, 0, dW1, D, s), "step/dW1");   // eq. (8) on codes
     else    STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, nullptr), "step/dW1");           // eq. (8), bf16

@@ -271,9 +271,14 @@ __global__ void __launch_bounds__(256) quantize_fp8_blocked_kernel(const uint16_
     note_amax_slots(amax, m);
 }
 
-// [R, C] bf16 -> codes of the transposed matrix [C, R] in the blocked pair layout; 64 x 64 tiles through LDS
+// [R, C] bf16 -> codes of the transposed matrix [C, R] in the blocked pair layout; 64 x 64 tiles through LDS.  While the tile is in
+// registers the same pass can also write (EXTRA 1) the codes in the source's own orientation, blocked (X, dY of the fp8 step with fp8
+// weight gradients), or (EXTRA 2) the 2:4 pruning of the rows (Section 2.2, HARD / SOFT): canonical codes [R, C/2] + metadata [R, C/8] +
+// the pruned codes blocked (W1 of the fp8 step: pruned for eq. (1), dense and transposed for eq. (7), one read).
+template <int EXTRA, bool SOFT>
 __global__ void __launch_bounds__(256) transpose_quantize_fp8_blocked_kernel(const uint16_t* __restrict__ src, int64_t R, int64_t C, int64_t ld, float inv,
-                                                                            uint16_t* __restrict__ out, float* __restrict__ amax) {
+                                                                            uint16_t* __restrict__ out, float* __restrict__ amax, uint16_t* __restrict__ out_same,
+                                                                            uint8_t* __restrict__ p_codes, uint8_t* __restrict__ p_meta, uint16_t* __restrict__ p_blk) {
     __shared__ uint16_t tile[64][64 + 2];
     const int tid = threadIdx.x;
     const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
@@ -283,6 +288,21 @@ __global__ void __launch_bounds__(256) transpose_quantize_fp8_blocked_kernel(con
         const uint4 w = *reinterpret_cast<const uint4*>(src + (r0 + r) * ld + c0 + seg * 8);
         uint32_t* d = reinterpret_cast<uint32_t*>(&tile[r][seg * 8]);
         d[0] = w.x; d[1] = w.y; d[2] = w.z; d[3] = w.w;
+        if (EXTRA == 1)
+            *reinterpret_cast<uint2*>(out_same + blk_off(r0 + r, (c0 + seg * 8) / 2, C / 64)) =
+                make_uint2(enc2(bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), inv) | (enc2(bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16), inv) << 16),
+                           enc2(bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), inv) | (enc2(bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16), inv) << 16));
+        if (EXTRA == 2) {
+            uint32_t n0, n1;
+            float a, b, d2, e;
+            select24_f32<SOFT>(w.x & 0xFFFFu, w.x >> 16, w.y & 0xFFFFu, w.y >> 16, n0, a, b);
+            select24_f32<SOFT>(w.z & 0xFFFFu, w.z >> 16, w.w & 0xFFFFu, w.w >> 16, n1, d2, e);
+            const uint32_t q4 = enc2(a, b, inv) | (enc2(d2, e, inv) << 16);
+            const int64_t cc = (c0 + seg * 8) / 8;                  // chunk of 8 columns inside the row
+            *reinterpret_cast<uint32_t*>(p_codes + (r0 + r) * (C / 2) + cc * 4) = q4;
+            p_meta[(r0 + r) * (C / 8) + cc] = (uint8_t)(n0 | (n1 << 4));
+            *reinterpret_cast<uint32_t*>(p_blk + blk_off(r0 + r, cc * 2, C / 128)) = q4;
+        }
     }
     __syncthreads();
     float m = 0.0f;
@@ -326,10 +346,17 @@ hipError_t launch_amax_finish(const float* slots, int n, float* out, hipStream_t
     return hipGetLastError();
 }
 
-hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s, float* amax) {
-    if (C % 64 != 0 || R % 64 != 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(transpose_quantize_fp8_blocked_kernel, dim3((unsigned)(C / 64), (unsigned)(R / 64)), dim3(256), 0, s, src, R, C, ld, inv,
-                       reinterpret_cast<uint16_t*>(out_t_blk), amax);
+hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s, float* amax,
+                                                 uint8_t* out_same_blk, int prune_mode, uint8_t* p_codes, uint8_t* p_meta, uint8_t* p_blk) {
+    if (C % 64 != 0 || R % 64 != 0 || (out_same_blk && p_codes) || (p_codes && (!p_meta || !p_blk || C % 128 != 0))) return hipErrorInvalidValue;
+    dim3 grid((unsigned)(C / 64), (unsigned)(R / 64));
+    uint16_t* o = reinterpret_cast<uint16_t*>(out_t_blk);
+#define SFFN_TQ(E, SOFT) hipLaunchKernelGGL((transpose_quantize_fp8_blocked_kernel<E, SOFT>), grid, dim3(256), 0, s, src, R, C, ld, inv, o, amax, \
+                                           reinterpret_cast<uint16_t*>(out_same_blk), p_codes, p_meta, reinterpret_cast<uint16_t*>(p_blk))
+    if (p_codes) { if (prune_mode == 0) SFFN_TQ(2, false); else SFFN_TQ(2, true); }
+    else if (out_same_blk) SFFN_TQ(1, false);
+    else SFFN_TQ(0, false);
+#undef SFFN_TQ
     return hipGetLastError();
 }
 

@@ -167,8 +167,11 @@ hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta
 // fp8.hip, producers of such operands: quantised copy in the same orientation / transposed; 2:4 pruning that also writes the blocked codes
 // (amax, optional: the tensor's amax slots, see below)
 hipError_t launch_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_blk, hipStream_t s, float* amax = nullptr);
+// (out_same_blk: also the codes in the source's orientation; p_codes / p_meta / p_blk: also the 2:4 pruning of the rows, mode prune_mode, canonical
+//  codes [R, C/2] + metadata [R, C/8] + blocked codes; at most one of the two extras)
 hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s,
-                                                 float* amax = nullptr);
+                                                 float* amax = nullptr, uint8_t* out_same_blk = nullptr, int prune_mode = 0, uint8_t* p_codes = nullptr,
+                                                 uint8_t* p_meta = nullptr, uint8_t* p_blk = nullptr);
 // amax slots of the fused fp8 step: n tensors x 64 slots x 256 bytes (kAmaxSlots, kAmaxSlotStride in common.hpp); the step's kernels take a tensor's slot base
 hipError_t launch_amax_clear(float* slots, int n, hipStream_t s);
 hipError_t launch_amax_finish(const float* slots, int n, float* out, hipStream_t s);
