@@ -210,6 +210,15 @@ int sffn_fp8_workspace_layout(const sffn_cfg* cfg, sffn_fp8_ws_layout* out);
 int ffn_sparse_step_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* scales, const uint16_t* X, const uint16_t* W1,
                         const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
                         uint16_t* dW2, void* workspace, size_t ws_bytes, float* amax, void* stream);
+/* The mixture-of-experts form (as ffn_sparse_step_grouped: expert e owns token rows seg_offsets[e] .. seg_offsets[e+1], a host array of
+ * n_experts + 1 ascending multiples of 64 from 0 to T; W1 [E, F, D], W2 [E, D, F], b1 [E, F], dW1 / dW2 likewise).  One scale per
+ * stacked tensor (all experts' W1 share s_w1, ...); amax likewise over all experts.  The contractions are one grouped launch per stage;
+ * the weight passes run once per expert.  Workspace: sffn_fp8_grouped_workspace_layout(cfg, n_experts, &l).total bytes. */
+int sffn_fp8_grouped_workspace_layout(const sffn_cfg* cfg, int n_experts, sffn_fp8_ws_layout* out);
+int ffn_sparse_step_fp8_grouped(const sffn_cfg* cfg, const sffn_fp8_scales* scales, int n_experts, const int64_t* seg_offsets,
+                                const uint16_t* X, const uint16_t* W1, const uint16_t* W2, const float* b1, const uint16_t* dY,
+                                uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes,
+                                float* amax, void* stream);
 
 /* Section 3.3 / Alg. 3 ("Convert Activation to Venom") and the conversion steps 1-3 of Section 3.4: neuron-level
  * experts that produce the V:N:M activation directly.  Reading built here: E = M/4 experts; expert e owns the hidden

@@ -18,4 +18,4 @@ from .ffn import ffn_sparse_step_ref, ffn_dense_ref, ffn_sparse_step_grouped_ref
 from .router import (route_scores, route_scores_plain, route_margin_is_clear, route_top1, expert_permutation, cluster_rows, expert_matmul, venom_from_compact,
                      moe_to_venom, scatter_compact, ffn_router_step_ref)
 from . import fp8
-from .fp8 import (e4m3_decode, e4m3_encode, quantize_fp8, prune24_compress_fp8, sqrelu_vnm_compress_fp8, spmm24_fp8, vnm_spmm_fp8, ffn_sparse_step_fp8_ref)
+from .fp8 import (e4m3_decode, e4m3_encode, quantize_fp8, prune24_compress_fp8, sqrelu_vnm_compress_fp8, spmm24_fp8, vnm_spmm_fp8, ffn_sparse_step_fp8_ref, ffn_sparse_step_fp8_grouped_ref)

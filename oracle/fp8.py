@@ -201,3 +201,18 @@ def ffn_sparse_step_fp8_ref(X, W1, W2, b1, dY, scales, mode=HARD, V=64, M=8, wgr
     return dict(amax=amax_of, xq=xq, w1_codes=w1_codes, w1_meta=w1_meta, y1=y1, y2_codes=y2_codes, y2_vals=y2_vals, y2_meta=y2_meta, colidx=colidx,
                 w2q=w2q, y3=y3, dyq=dyq, w2t_codes=w2t_codes, w2t_meta=w2t_meta, dy2=dy2, dW2=dW2, dy1_vals=dy1_vals,
                 dy1_codes=dy1_codes, w1q=w1q, dX=dX, dW1=dW1)
+
+
+def ffn_sparse_step_fp8_grouped_ref(X, W1, W2, b1, dY, seg_offsets, scales, mode=HARD, V=64, M=8, wgrad_fp8=False):
+    """Mixture-of-experts form of the fp8 step (Section 1: the method applies to MoE FFNs, each expert being one FFN of Alg. 1 /
+    Alg. 2): expert e owns rows seg_offsets[e]..seg_offsets[e+1] of X and dY and its own W1[e], W2[e], b1[e]; the six scales are
+    shared by all experts.  Returns one ffn_sparse_step_fp8_ref result per expert (None for an expert without rows; its weight
+    gradients are zero by the empty sum)."""
+    res = []
+    for e in range(len(seg_offsets) - 1):
+        a, b = int(seg_offsets[e]), int(seg_offsets[e + 1])
+        if b == a:
+            res.append(None)
+            continue
+        res.append(ffn_sparse_step_fp8_ref(X[a:b], W1[e], W2[e], None if b1 is None else b1[e], dY[a:b], scales, mode, V, M, wgrad_fp8))
+    return res

@@ -10,4 +10,4 @@ from .binding import (SffnError, lib_path, load, version, workspace_bytes, works
                       MODE_HARD, MODE_SOFT, FLAG_KEEP_DENSE, FLAG_UNFUSED, FLAG_FP8_WGRAD, profile_enable, profile_read, dense_sqrelu, dense_dsqrelu,
                       ffn_sparse_step_noalloc, NOALLOC_WORKSPACE_MAX,
                       prune24_compress_prepared, spmm24_prepared,
-                      quantize_fp8, prune24_compress_fp8, sqrelu_vnm_compress_fp8, spmm24_fp8, vnm_spmm_fp8, FfnStepFp8)
+                      quantize_fp8, prune24_compress_fp8, sqrelu_vnm_compress_fp8, spmm24_fp8, vnm_spmm_fp8, FfnStepFp8, FfnStepFp8Grouped)

@@ -110,6 +110,8 @@ def load():
     lib.sffn_fp8_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg)]
     lib.sffn_fp8_workspace_layout.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Layout)]
     lib.ffn_sparse_step_fp8.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Scales), p, p, p, p, p, p, p, p, p, p, sz, p, p]
+    lib.sffn_fp8_grouped_workspace_layout.argtypes = [ctypes.POINTER(_Cfg), i32, ctypes.POINTER(_Fp8Layout)]
+    lib.ffn_sparse_step_fp8_grouped.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Scales), i32, p, p, p, p, p, p, p, p, p, p, p, sz, p, p]
     lib.sffn_dense_sqrelu.argtypes = [p, p, i64, p]
     lib.sffn_dense_dsqrelu.argtypes = [p, p, p, i64, p]
     lib.sffn_profile_enable.argtypes = [i32]
@@ -568,6 +570,57 @@ class FfnStepFp8:
         u8 = torch.uint8
         out = dict(w1_codes=view(L["w1_codes"], (F, D // 2), u8), w1_meta=view(L["w1_meta"], (F, D // 8), u8),
                    w2t_codes=view(L["w2t_codes"], (F, D // 2), u8), w2t_meta=view(L["w2t_meta"], (F, D // 8), u8),
+                   y2_codes=view(L["y2_codes"], (T, F // 4), u8), y2_meta=view(L["y2_meta"], (T, F // 16), u8),
+                   colidx=view(L["colidx"], (T // 64, F // 8, 4), u8), dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16),
+                   y1_kept=view(L["y1_kept"], (T, F // 4), torch.bfloat16))
+        if self.keep_dense:
+            out["y1"], out["dy2"] = view(L["y1"], (T, F), torch.bfloat16), view(L["dy2"], (T, F), torch.bfloat16)
+        return out
+
+
+class FfnStepFp8Grouped(FfnStepFp8):
+    """ffn_sparse_step_fp8_grouped: n_experts FFNs, expert e on token rows seg[e]..seg[e+1] (host integers, multiples of 64; T = seg[-1])."""
+
+    def __init__(self, seg, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False):
+        self.seg = [int(v) for v in seg]
+        self.E, self.T, self.D, self.F, self.mode, self.keep_dense = len(self.seg) - 1, self.seg[-1], D, F, mode, keep_dense
+        self.seg_c = (ctypes.c_int64 * len(self.seg))(*self.seg)
+        self.cfg = _cfg(self.T, D, F, mode, M=8, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0))
+        self.set_scales(scales)
+        lay = _Fp8Layout()
+        _check(load().sffn_fp8_grouped_workspace_layout(ctypes.byref(self.cfg), self.E, ctypes.byref(lay)))
+        self.layout = {n: getattr(lay, n) for n, _ in _Fp8Layout._fields_}
+        self.ws = _u8((self.layout["total"],), device)
+        self.Y3, self.dX = _bf16((self.T, D), device), _bf16((self.T, D), device)
+        self.dW1, self.dW2 = _bf16((self.E, F, D), device), _bf16((self.E, D, F), device)
+        self.amax = torch.zeros((8,), dtype=torch.float32, device=device)
+
+    def __call__(self, X, W1, W2, b1, dY):
+        T, D, F, E = self.T, self.D, self.F, self.E
+        _want("ffn_sparse_step_fp8_grouped: X", X, (T, D), _BF16)
+        _want("ffn_sparse_step_fp8_grouped: W1", W1, (E, F, D), _BF16)
+        _want("ffn_sparse_step_fp8_grouped: W2", W2, (E, D, F), _BF16)
+        _want("ffn_sparse_step_fp8_grouped: b1", b1, (E, F), _F32, optional=True)
+        _want("ffn_sparse_step_fp8_grouped: dY", dY, (T, D), _BF16)
+        _check(load().ffn_sparse_step_fp8_grouped(ctypes.byref(self.cfg), ctypes.byref(self.scales), self.E, self.seg_c, _ptr(X), _ptr(W1), _ptr(W2),
+                                                  _ptr(b1), _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws),
+                                                  self.layout["total"], _ptr(self.amax), _stream()))
+        return self.Y3, self.dX, self.dW1, self.dW2
+
+    def saved(self):
+        """As FfnStepFp8.saved(); weight-shaped tensors carry a leading expert axis."""
+        T, D, F, E, L = self.T, self.D, self.F, self.E, self.layout
+
+        def view(off, shape, dtype):
+            n = 1
+            for d in shape:
+                n *= d
+            nbytes = n * (2 if dtype == torch.bfloat16 else 1)
+            return self.ws[off:off + nbytes].view(dtype).view(shape)
+
+        u8 = torch.uint8
+        out = dict(w1_codes=view(L["w1_codes"], (E, F, D // 2), u8), w1_meta=view(L["w1_meta"], (E, F, D // 8), u8),
+                   w2t_codes=view(L["w2t_codes"], (E, F, D // 2), u8), w2t_meta=view(L["w2t_meta"], (E, F, D // 8), u8),
                    y2_codes=view(L["y2_codes"], (T, F // 4), u8), y2_meta=view(L["y2_meta"], (T, F // 16), u8),
                    colidx=view(L["colidx"], (T // 64, F // 8, 4), u8), dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16),
                    y1_kept=view(L["y1_kept"], (T, F // 4), torch.bfloat16))

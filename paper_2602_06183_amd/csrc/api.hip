@@ -384,11 +384,12 @@ struct Fp8Layout {
     sffn_fp8_ws_layout pub;
     size_t w1_blk, w2t_blk, xq, xt_blk, dyq, dyt_blk, w2q, w1tq, v24, m24, at_blk, kmask, amax_slots, total;
 };
-bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L) {
-    if (!c || !mult64(c->T) || !mult128(c->D) || !mult128(c->F) || c->V != 64 || c->M != 8) return false;
+// E = number of experts (1 for the plain step): weight-shaped tensors hold E matrices back to back
+bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L, int n_experts = 1) {
+    if (!c || !mult64(c->T) || !mult128(c->D) || !mult128(c->F) || c->V != 64 || c->M != 8 || n_experts < 1) return false;
     if (c->flags & ~(SFFN_FLAG_KEEP_DENSE | SFFN_FLAG_FP8_WGRAD)) return false;
     const bool dense = (c->flags & SFFN_FLAG_KEEP_DENSE) != 0;
-    const size_t T = c->T, D = c->D, F = c->F, TF = T * F;
+    const size_t T = c->T, D = c->D, F = (size_t)c->F * n_experts, TF = T * (size_t)c->F;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
     L->pub.w1_codes = take(F * D / 2);     L->pub.w1_meta = take(F * D / 8);
@@ -408,6 +409,103 @@ bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L) {
     L->pub.total = off;
     return true;
 }
+
+int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, const int64_t* seg, const uint16_t* X, const uint16_t* W1,
+                 const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace,
+                 size_t ws_bytes, float* amax, void* stream) {
+    REQUIRE(cfg != nullptr && sc != nullptr, SFFN_EINVAL, "ffn_sparse_step_fp8: cfg or scales is null");
+    REQUIRE(aligned16(amax), SFFN_EINVAL, "ffn_sparse_step_fp8: amax must be 16-byte aligned");
+    Fp8Layout L;
+    REQUIRE(n_experts >= 1 && n_experts <= GemmGroup::kMaxExperts, SFFN_EINVAL, "ffn_sparse_step_fp8_grouped: n_experts must be in 1..64");
+    REQUIRE(cfg->M == 8 && cfg->V == 64, SFFN_EUNSUPPORTED, "ffn_sparse_step_fp8: only V = 64, M = 8 is built");
+    REQUIRE(make_fp8_layout(cfg, &L, n_experts), SFFN_EINVAL,
+            "ffn_sparse_step_fp8: T must be a positive multiple of 64, D and F of 128; flags: SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD");
+    REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_sparse_step_fp8: unknown mode");
+    REQUIRE(X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_sparse_step_fp8: null pointer");
+    REQUIRE(aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(dY) && aligned16(Y3) && aligned16(dX) && aligned16(dW1) && aligned16(dW2) &&
+            aligned16(b1) && aligned16(workspace), SFFN_EINVAL, "ffn_sparse_step_fp8: pointers must be 16-byte aligned");
+    REQUIRE(scale_ok(sc->x) && scale_ok(sc->w1) && scale_ok(sc->w2) && scale_ok(sc->y2) && scale_ok(sc->dy) && scale_ok(sc->dy1), SFFN_EINVAL,
+            "ffn_sparse_step_fp8: scales must be positive finite floats");
+    const int64_t T = cfg->T, D = cfg->D, F = cfg->F, E = n_experts;
+    REQUIRE(fits_int(T) && fits_int(D) && fits_int(F * E) && T / 64 < 65536 && F * D < ((int64_t)1 << 32) && T * D < ((int64_t)1 << 32), SFFN_EUNSUPPORTED,
+            "ffn_sparse_step_fp8: dimension too large");
+    GemmGroup g;                                    // g.n = 0: plain step
+    if (seg) {
+        REQUIRE(seg[0] == 0 && seg[E] == T, SFFN_EINVAL, "ffn_sparse_step_fp8_grouped: seg_offsets must start at 0 and end at T");
+        for (int e = 0; e < E; ++e)
+            REQUIRE(seg[e + 1] >= seg[e] && seg[e + 1] % 64 == 0, SFFN_EINVAL, "ffn_sparse_step_fp8_grouped: seg_offsets must be ascending multiples of 64");
+        g.n = (int)E;
+        for (int e = 0; e <= E; ++e) g.seg[e] = (int32_t)seg[e];
+    }
+    REQUIRE(workspace && ws_bytes >= L.total, SFFN_EWORKSPACE, "ffn_sparse_step_fp8: workspace missing or too small (sffn_fp8_workspace_bytes)");
+    hipStream_t s = (hipStream_t)stream;
+    uint8_t* ws = (uint8_t*)workspace;
+    uint8_t *w1c = ws + L.pub.w1_codes, *w1m = ws + L.pub.w1_meta, *w2c = ws + L.pub.w2t_codes, *w2m = ws + L.pub.w2t_meta;
+    uint16_t *y1 = (uint16_t*)(ws + L.pub.y1), *dy2 = (uint16_t*)(ws + L.pub.dy2), *dy1v = (uint16_t*)(ws + L.pub.dy1_vals), *ykept = (uint16_t*)(ws + L.pub.y1_kept);
+    uint8_t *y2c = ws + L.pub.y2_codes, *y2m = ws + L.pub.y2_meta, *cix = ws + L.pub.colidx;
+    uint8_t *w1b = ws + L.w1_blk, *w2b = ws + L.w2t_blk, *xq = ws + L.xq, *dyq = ws + L.dyq, *w2q = ws + L.w2q, *w1tq = ws + L.w1tq;
+    uint16_t *xtb = (uint16_t*)(ws + L.xt_blk), *dytb = (uint16_t*)(ws + L.dyt_blk), *atb = (uint16_t*)(ws + L.at_blk);
+    uint8_t *v24 = ws + L.v24, *m24 = ws + L.m24, *kmask = ws + L.kmask;
+    const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
+    const bool w8 = (cfg->flags & SFFN_FLAG_FP8_WGRAD) != 0;      // eqs. (5), (8) on codes too: X.T, dY.T and the compact transposed survivors as codes
+    const float ix = 1.0f / sc->x, iw1 = 1.0f / sc->w1, iw2 = 1.0f / sc->w2, idy = 1.0f / sc->dy;
+    // the three ways a token segment meets its expert's weights (see GemmGroup); strides in the units the kernels index: pairs of codes
+    GemmGroup g_packed = g, g_dense = g, g_wgrad = g;
+    g_packed.role = 1; g_packed.a_stride = F * D / 4; g_packed.m_stride = F * D / 8; g_packed.bias_stride = F;
+    g_dense.role = 0;  g_dense.b_stride = D * F / 2;
+    g_wgrad.role = 2;  g_wgrad.out_stride = D * F;
+    const GemmGroup* gp = g.n ? &g_packed : nullptr;
+    const GemmGroup* gd = g.n ? &g_dense : nullptr;
+    const GemmGroup* gw = g.n ? &g_wgrad : nullptr;
+    // amax[0..5] = largest magnitude of x, w1, w2, y2's survivors, dy, dy1's survivors (what next step's scales are made of)
+    // (collected in 64 slots per tensor inside the workspace, folded by the last launch)
+    float* slots = amax ? (float*)(ws + L.amax_slots) : nullptr;
+    auto slot_of = [&](int i) { return slots ? slots + (size_t)i * 64 * 64 : nullptr; };
+    float *ax = slot_of(0), *aw1 = slot_of(1), *aw2 = slot_of(2), *ay2 = slot_of(3), *ady = slot_of(4), *ady1 = slot_of(5);
+    if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
+    if (amax) STAGE(launch_amax_clear(slots, 6, s), "step/clear(amax)");
+    // ---- Alg. 1 -------------------------------------------------------------------------------
+    if (w8) {       // X.T codes for eq. (8) and X codes for eq. (1) in one pass over X
+        STAGE(launch_transpose_quantize_fp8_blocked(X, T, D, D, ix, (uint8_t*)xtb, s, ax, xq), "step/quantize(X, X.T)");
+    } else {
+        STAGE(launch_transpose(X, T, D, D, xtb, 1, nullptr, s), "step/X.T");                                // bf16, for eq. (8)
+        STAGE(launch_quantize_fp8_blocked(X, T, D, D, ix, xq, s, ax), "step/quantize(X)");
+    }
+    // W1 in one pass per expert: pruned (canonical + blocked codes) for eq. (1), dense and transposed for eq. (7)
+    for (int64_t e = 0; e < E; ++e)
+        STAGE(launch_transpose_quantize_fp8_blocked(W1 + e * F * D, F, D, D, iw1, w1tq + e * D * F, s, aw1, nullptr, cfg->mode, w1c + e * F * D / 2,
+                                                    w1m + e * F * D / 8, w1b + e * F * D / 2), "step/prune24_fp8(W1)+quantize(W1.T)");
+    {   // eq. (1) on codes, then eq. (2) + V:N:M compression on the bf16 tile; the survivors leave as codes (and in bf16 for eq. (5))
+        VnmEpilogue ep;
+        ep.mode = 1; ep.store_dense = keep_dense; ep.vals = (uint16_t*)y2c; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
+        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->y2; ep.at_fp8 = w8; ep.amax = ay2;
+        STAGE(launch_gemm_fp8_blocked(w1b, w1m, xq, b1, sc->x * sc->w1, F, T, D, y1, F, &ep, s, gp), "step/y1+sqrelu_vnm_compress");
+    }
+    for (int64_t e = 0; e < E; ++e)
+        STAGE(launch_prune24_fp8_step(W2 + e * D * F, F, D, F, 1, cfg->mode, iw2, w2c + e * F * D / 2, w2m + e * F * D / 8, w2b + e * F * D / 2, s,
+                                      w2q + e * D * F, aw2), "step/prune24_fp8(W2.T)+quantize(W2)");
+    STAGE(launch_gemm_fp8_blocked(v24, m24, w2q, nullptr, sc->y2 * sc->w2, T, D, F, Y3, D, nullptr, s, gd), "step/y3");      // eq. (3)
+    // ---- Alg. 2 -------------------------------------------------------------------------------
+    if (w8) {
+        STAGE(launch_transpose_quantize_fp8_blocked(dY, T, D, D, idy, (uint8_t*)dytb, s, ady, dyq), "step/quantize(dY, dY.T)");
+    } else {
+        STAGE(launch_transpose(dY, T, D, D, dytb, 1, nullptr, s), "step/dY.T");                             // bf16, for eq. (5)
+        STAGE(launch_quantize_fp8_blocked(dY, T, D, D, idy, dyq, s, ady), "step/quantize(dY)");
+    }
+    if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)dytb, sc->y2 * sc->dy, F, D, T, 1, dW2, F, s, gw), "step/dW2");   // eq. (5) on codes
+    else    STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");               // eq. (5), bf16
+    {   // eq. (4) on codes, then eq. (6) in bf16 on y2's kept slots; dy1 leaves in bf16 (canonical, eq. (8)) and as codes (eq. (7))
+        VnmEpilogue ep;
+        ep.mode = 2; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
+        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->dy1; ep.at_fp8 = w8; ep.amax = ady1;
+        STAGE(launch_gemm_fp8_blocked(w2b, w2m, dyq, nullptr, sc->dy * sc->w2, F, T, D, dy2, F, &ep, s, gp), "step/dy2+dsqrelu_vnm");
+    }
+    STAGE(launch_gemm_fp8_blocked(v24, m24, w1tq, nullptr, sc->dy1 * sc->w1, T, D, F, dX, D, nullptr, s, gd), "step/dX");      // eq. (7)
+    if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)xtb, sc->dy1 * sc->x, F, D, T, 0, dW1, D, s, gw), "step/dW1");   // eq. (8) on codes
+    else    STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                // eq. (8), bf16
+    if (amax) STAGE(launch_amax_finish(slots, 6, amax, s), "step/finish(amax)");
+    return SFFN_OK;
+}
 }  // namespace
 
 size_t sffn_fp8_workspace_bytes(const sffn_cfg* cfg) {
@@ -423,79 +521,26 @@ int sffn_fp8_workspace_layout(const sffn_cfg* cfg, sffn_fp8_ws_layout* out) {
     return SFFN_OK;
 }
 
+int sffn_fp8_grouped_workspace_layout(const sffn_cfg* cfg, int n_experts, sffn_fp8_ws_layout* out) {
+    Fp8Layout L;
+    REQUIRE(out != nullptr, SFFN_EINVAL, "sffn_fp8_grouped_workspace_layout: out is null");
+    REQUIRE(make_fp8_layout(cfg, &L, n_experts), SFFN_EINVAL,
+            "sffn_fp8_grouped_workspace_layout: T a multiple of 64, D and F of 128, V = 64, M = 8, n_experts >= 1, flags: SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD");
+    *out = L.pub;
+    return SFFN_OK;
+}
+
 int ffn_sparse_step_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* sc, const uint16_t* X, const uint16_t* W1, const uint16_t* W2, const float* b1,
                         const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, float* amax,
                         void* stream) {
-    REQUIRE(cfg != nullptr && sc != nullptr, SFFN_EINVAL, "ffn_sparse_step_fp8: cfg or scales is null");
-    REQUIRE(aligned16(amax), SFFN_EINVAL, "ffn_sparse_step_fp8: amax must be 16-byte aligned");
-    Fp8Layout L;
-    REQUIRE(cfg->M == 8 && cfg->V == 64, SFFN_EUNSUPPORTED, "ffn_sparse_step_fp8: only V = 64, M = 8 is built");
-    REQUIRE(make_fp8_layout(cfg, &L), SFFN_EINVAL, "ffn_sparse_step_fp8: T must be a positive multiple of 64, D and F of 128; flags: SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD");
-    REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_sparse_step_fp8: unknown mode");
-    REQUIRE(X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_sparse_step_fp8: null pointer");
-    REQUIRE(aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(dY) && aligned16(Y3) && aligned16(dX) && aligned16(dW1) && aligned16(dW2) &&
-            aligned16(b1) && aligned16(workspace), SFFN_EINVAL, "ffn_sparse_step_fp8: pointers must be 16-byte aligned");
-    REQUIRE(scale_ok(sc->x) && scale_ok(sc->w1) && scale_ok(sc->w2) && scale_ok(sc->y2) && scale_ok(sc->dy) && scale_ok(sc->dy1), SFFN_EINVAL,
-            "ffn_sparse_step_fp8: scales must be positive finite floats");
-    const int64_t T = cfg->T, D = cfg->D, F = cfg->F;
-    REQUIRE(fits_int(T) && fits_int(D) && fits_int(F) && T / 64 < 65536 && F * D < ((int64_t)1 << 32) && T * D < ((int64_t)1 << 32), SFFN_EUNSUPPORTED,
-            "ffn_sparse_step_fp8: dimension too large");
-    REQUIRE(workspace && ws_bytes >= L.total, SFFN_EWORKSPACE, "ffn_sparse_step_fp8: workspace missing or too small (sffn_fp8_workspace_bytes)");
-    hipStream_t s = (hipStream_t)stream;
-    uint8_t* ws = (uint8_t*)workspace;
-    uint8_t *w1c = ws + L.pub.w1_codes, *w1m = ws + L.pub.w1_meta, *w2c = ws + L.pub.w2t_codes, *w2m = ws + L.pub.w2t_meta;
-    uint16_t *y1 = (uint16_t*)(ws + L.pub.y1), *dy2 = (uint16_t*)(ws + L.pub.dy2), *dy1v = (uint16_t*)(ws + L.pub.dy1_vals), *ykept = (uint16_t*)(ws + L.pub.y1_kept);
-    uint8_t *y2c = ws + L.pub.y2_codes, *y2m = ws + L.pub.y2_meta, *cix = ws + L.pub.colidx;
-    uint8_t *w1b = ws + L.w1_blk, *w2b = ws + L.w2t_blk, *xq = ws + L.xq, *dyq = ws + L.dyq, *w2q = ws + L.w2q, *w1tq = ws + L.w1tq;
-    uint16_t *xtb = (uint16_t*)(ws + L.xt_blk), *dytb = (uint16_t*)(ws + L.dyt_blk), *atb = (uint16_t*)(ws + L.at_blk);
-    uint8_t *v24 = ws + L.v24, *m24 = ws + L.m24, *kmask = ws + L.kmask;
-    const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
-    const bool w8 = (cfg->flags & SFFN_FLAG_FP8_WGRAD) != 0;      // eqs. (5), (8) on codes too: X.T, dY.T and the compact transposed survivors as codes
-    const float ix = 1.0f / sc->x, iw1 = 1.0f / sc->w1, iw2 = 1.0f / sc->w2, idy = 1.0f / sc->dy;
-    // amax[0..5] = largest magnitude of x, w1, w2, y2's survivors, dy, dy1's survivors (what next step's scales are made of)
-    // (collected in 64 slots per tensor inside the workspace, folded by the last launch)
-    float* slots = amax ? (float*)(ws + L.amax_slots) : nullptr;
-    auto slot_of = [&](int i) { return slots ? slots + (size_t)i * 64 * 64 : nullptr; };
-    float *ax = slot_of(0), *aw1 = slot_of(1), *aw2 = slot_of(2), *ay2 = slot_of(3), *ady = slot_of(4), *ady1 = slot_of(5);
-    if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
-    if (amax) STAGE(launch_amax_clear(slots, 6, s), "step/clear(amax)");
-    // ---- Alg. 1 -------------------------------------------------------------------------------
-    if (w8) {       // X.T codes for eq. (8) and X codes for eq. (1) in one pass over X
-        STAGE(launch_transpose_quantize_fp8_blocked(X, T, D, D, ix, (uint8_t*)xtb, s, ax, xq), "step/quantize(X, X.T)");
-    } else {
-        STAGE(launch_transpose(X, T, D, D, xtb, 1, nullptr, s), "step/X.T");                                // bf16, for eq. (8)
-        STAGE(launch_quantize_fp8_blocked(X, T, D, D, ix, xq, s, ax), "step/quantize(X)");
-    }
-    // W1 in one pass: pruned (canonical + blocked codes) for eq. (1), dense and transposed for eq. (7)
-    STAGE(launch_transpose_quantize_fp8_blocked(W1, F, D, D, iw1, w1tq, s, aw1, nullptr, cfg->mode, w1c, w1m, w1b), "step/prune24_fp8(W1)+quantize(W1.T)");
-    {   // eq. (1) on codes, then eq. (2) + V:N:M compression on the bf16 tile; the survivors leave as codes (and in bf16 for eq. (5))
-        VnmEpilogue ep;
-        ep.mode = 1; ep.store_dense = keep_dense; ep.vals = (uint16_t*)y2c; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
-        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->y2; ep.at_fp8 = w8; ep.amax = ay2;
-        STAGE(launch_gemm_fp8_blocked(w1b, w1m, xq, b1, sc->x * sc->w1, F, T, D, y1, F, &ep, s), "step/y1+sqrelu_vnm_compress");
-    }
-    STAGE(launch_prune24_fp8_step(W2, F, D, F, 1, cfg->mode, iw2, w2c, w2m, w2b, s, w2q, aw2), "step/prune24_fp8(W2.T)+quantize(W2)");
-    STAGE(launch_gemm_fp8_blocked(v24, m24, w2q, nullptr, sc->y2 * sc->w2, T, D, F, Y3, D, nullptr, s), "step/y3");      // eq. (3)
-    // ---- Alg. 2 -------------------------------------------------------------------------------
-    if (w8) {
-        STAGE(launch_transpose_quantize_fp8_blocked(dY, T, D, D, idy, (uint8_t*)dytb, s, ady, dyq), "step/quantize(dY, dY.T)");
-    } else {
-        STAGE(launch_transpose(dY, T, D, D, dytb, 1, nullptr, s), "step/dY.T");                             // bf16, for eq. (5)
-        STAGE(launch_quantize_fp8_blocked(dY, T, D, D, idy, dyq, s, ady), "step/quantize(dY)");
-    }
-    if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)dytb, sc->y2 * sc->dy, F, D, T, 1, dW2, F, s), "step/dW2");   // eq. (5) on codes
-    else    STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, nullptr), "step/dW2");          // eq. (5), bf16
-    {   // eq. (4) on codes, then eq. (6) in bf16 on y2's kept slots; dy1 leaves in bf16 (canonical, eq. (8)) and as codes (eq. (7))
-        VnmEpilogue ep;
-        ep.mode = 2; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
-        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->dy1; ep.at_fp8 = w8; ep.amax = ady1;
-        STAGE(launch_gemm_fp8_blocked(w2b, w2m, dyq, nullptr, sc->dy * sc->w2, F, T, D, dy2, F, &ep, s), "step/dy2+dsqrelu_vnm");
-    }
-    STAGE(launch_gemm_fp8_blocked(v24, m24, w1tq, nullptr, sc->dy1 * sc->w1, T, D, F, dX, D, nullptr, s), "step/dX");      // eq. (7)
-    if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)xtb, sc->dy1 * sc->x, F, D, T, 0, dW1, D, s), "step/dW1");   // eq. (8) on codes
-    else    STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, nullptr), "step/dW1");           // eq. (8), bf16
-    if (amax) STAGE(launch_amax_finish(slots, 6, amax, s), "step/finish(amax)");
-    return SFFN_OK;
+    return run_fp8_step(cfg, sc, 1, nullptr, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, ws_bytes, amax, stream);
+}
+
+int ffn_sparse_step_fp8_grouped(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, const int64_t* seg_offsets, const uint16_t* X,
+                                const uint16_t* W1, const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
+                                uint16_t* dW2, void* workspace, size_t ws_bytes, float* amax, void* stream) {
+    REQUIRE(seg_offsets != nullptr, SFFN_EINVAL, "ffn_sparse_step_fp8_grouped: seg_offsets is null");
+    return run_fp8_step(cfg, sc, n_experts, seg_offsets, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, ws_bytes, amax, stream);
 }
 
 // ---- Section 3.3 / Alg. 3: neuron-level experts that emit the V:N:M format ----------------------------------------

@@ -783,12 +783,16 @@ hipError_t launch_spmm24_fp8(const uint8_t* a_codes, const uint8_t* a_meta, cons
 }
 
 hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* Bq, const float* bias, float alpha, int64_t Ra,
-                                   int64_t Rb, int64_t K, uint16_t* out, int64_t ldo, const VnmEpilogue* ep, hipStream_t s) {
+                                   int64_t Rb, int64_t K, uint16_t* out, int64_t ldo, const VnmEpilogue* ep, hipStream_t s, const GemmGroup* grp) {
     if (K % 128 != 0 || (ep && ep->mode != 1 && ep->mode != 2)) return hipErrorInvalidValue;
     const int tiles_m = (int)((Ra + 255) / 256), tiles_n = (int)((Rb + 255) / 256);
     const VnmEpilogue e = ep ? *ep : VnmEpilogue();
-    const GemmGroup g;
-    dim3 grid((unsigned)(tiles_m * tiles_n));
+    const GemmGroup g = grp ? *grp : GemmGroup();
+    // grouped: the tokens are the j rows under an epilogue (role 1: A = the expert's packed weights), the i rows otherwise (role 0)
+    if (g.n && (g.n > GemmGroup::kMaxExperts || g.role != (ep ? 1 : 0) || g.seg_dev)) return hipErrorInvalidValue;
+    const unsigned tiles = grid_tiles(tiles_m, tiles_n, g);
+    if (tiles == 0) return hipSuccess;
+    dim3 grid(tiles);
     const uint16_t* a = reinterpret_cast<const uint16_t*>(a_codes);
     const uint16_t* b = reinterpret_cast<const uint16_t*>(Bq);
 #define SFFN_F8(ICONTIG, E) hipLaunchKernelGGL((gemm_nt_v2_kernel<true, ICONTIG, E, true, true>), grid, dim3(512), 0, s, a, a_meta, b, bias, (int)Ra, (int)Rb, \

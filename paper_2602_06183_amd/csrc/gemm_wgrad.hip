@@ -310,7 +310,7 @@ constexpr int k8Loads = 1 + 1 + 2;               // mask, A block, two G blocks 
 template <bool OUT_I_CONTIG>
 __global__ void __launch_bounds__(512) wgrad_vnm_fp8_kernel(const uint16_t* __restrict__ atc, const uint8_t* __restrict__ kmask,
                                                            const uint16_t* __restrict__ G, int F, int N, int Ttot, float alpha,
-                                                           uint16_t* __restrict__ out, int64_t ldo, int tiles_m, int tiles_n) {
+                                                           uint16_t* __restrict__ out, int64_t ldo, int tiles_m, int tiles_n, GemmGroup grp) {
     constexpr int BM = 256, BN = 256, WM = 128, WN = 64, FM = 4, FN = 2;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[k8Stages * k8Stage];
     static_assert(8 * 64 * (64 * 2 + 16) <= sizeof(smem), "epilogue scratch must fit");
@@ -323,6 +323,14 @@ __global__ void __launch_bounds__(512) wgrad_vnm_fp8_kernel(const uint16_t* __re
     {
         const int n = gridDim.x, pid = blockIdx.x, per = n >> 3;
         L = (pid < per * 8) ? (pid & 7) * per + (pid >> 3) : pid;
+    }
+    int k_base = 0, K = Ttot;                     // grouped: every expert contracts over its own token segment
+    if (grp.n) {
+        const int per = tiles_m * tiles_n, e = L / per;
+        L -= e * per;
+        k_base = grp.seg[e];
+        K = grp.seg[e + 1] - k_base;
+        out += e * grp.out_stride;
     }
     int tm, tn;
     {
@@ -340,13 +348,13 @@ __global__ void __launch_bounds__(512) wgrad_vnm_fp8_kernel(const uint16_t* __re
     const uint32_t blk_lane = (uint32_t)(rb * 32 + ((lane & 3) ^ ((rb >> 2) & 3)) * 8) * 2;   // chunk swizzle, as in the bf16 kernel
     {
         int cr = i0 / 2 + wave * 16; cr = cr < F / 2 ? cr : F / 2 - 16;
-        a_base = uniform64(atc + (((int64_t)(cr >> 4) * KC) << 9));
+        a_base = uniform64(atc + (((int64_t)(cr >> 4) * KC + k_base / 64) << 9));
 #pragma unroll
         for (int n = 0; n < 2; ++n) {
             int gr = j0 + (wave * 2 + n) * 16; gr = gr < N ? gr : N - 16;
-            b_base[n] = uniform64(G + (((int64_t)(gr >> 4) * KC) << 9));
+            b_base[n] = uniform64(G + (((int64_t)(gr >> 4) * KC + k_base / 64) << 9));
         }
-        c_base = uniform64(kmask);
+        c_base = uniform64(kmask + (int64_t)(k_base / 64) * (F / 8));
     }
     uint32_t c_lane;
     {
@@ -409,8 +417,8 @@ __global__ void __launch_bounds__(512) wgrad_vnm_fp8_kernel(const uint16_t* __re
             acc[a][b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa.q, fb[b].q, acc[a][b], 0, 0, 0, 0x7F, 0, 0x7F);   // fp8 x fp8, scales 2^0
     };
 #define SB() __builtin_amdgcn_sched_barrier(0)
-    const int nk = Ttot / 64;
-    {
+    const int nk = K / 64;                // 0 for an expert without tokens: its gradient is zero
+    if (nk > 0) {
         if (tid < k8Stages * 16) *reinterpret_cast<uint32_t*>(smem + (tid >> 4) * k8Stage + 128 * 64 + (tid & 15) * 4) = 0u;   // the rows of zeros
 #pragma unroll
         for (int p = 0; p < k8Stages; ++p) issue(p < nk ? p : nk - 1, p);
@@ -464,16 +472,18 @@ __global__ void __launch_bounds__(512) wgrad_vnm_fp8_kernel(const uint16_t* __re
 }
 
 hipError_t launch_wgrad_vnm_fp8(const uint8_t* atc, const uint8_t* kmask, const uint8_t* Gq, float alpha, int64_t F, int64_t N, int64_t T,
-                                int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s) {
+                                int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp) {
     if (T % 64 != 0 || T <= 0) return hipErrorInvalidValue;
     const int tiles_m = (int)((F + 255) / 256), tiles_n = (int)((N + 255) / 256);
-    dim3 grid((unsigned)(tiles_m * tiles_n));
+    const GemmGroup gg = grp ? *grp : GemmGroup();
+    if (gg.n && (gg.n > GemmGroup::kMaxExperts || gg.role != 2)) return hipErrorInvalidValue;
+    dim3 grid((unsigned)(tiles_m * tiles_n * (gg.n ? gg.n : 1)));
     const uint16_t* a = reinterpret_cast<const uint16_t*>(atc);
     const uint16_t* g = reinterpret_cast<const uint16_t*>(Gq);
     if (out_i_contig)
-        hipLaunchKernelGGL((wgrad_vnm_fp8_kernel<true>), grid, dim3(512), 0, s, a, kmask, g, (int)F, (int)N, (int)T, alpha, out, ldo, tiles_m, tiles_n);
+        hipLaunchKernelGGL((wgrad_vnm_fp8_kernel<true>), grid, dim3(512), 0, s, a, kmask, g, (int)F, (int)N, (int)T, alpha, out, ldo, tiles_m, tiles_n, gg);
     else
-        hipLaunchKernelGGL((wgrad_vnm_fp8_kernel<false>), grid, dim3(512), 0, s, a, kmask, g, (int)F, (int)N, (int)T, alpha, out, ldo, tiles_m, tiles_n);
+        hipLaunchKernelGGL((wgrad_vnm_fp8_kernel<false>), grid, dim3(512), 0, s, a, kmask, g, (int)F, (int)N, (int)T, alpha, out, ldo, tiles_m, tiles_n, gg);
     return hipGetLastError();
 }
 

@@ -163,7 +163,7 @@ hipError_t launch_spmm24_fp8(const uint8_t* a_codes, const uint8_t* a_meta, cons
 // codes [Ra, K/2], a_meta row-major [Ra, K/8], Bq = codes [Rb, K].  ep = nullptr: out[i * ldo + j] (eqs. (3), (7): Ra = tokens);
 // ep (mode 1 or 2, M = 8): eq. (1) / eq. (4) with the fused V:N:M epilogue, Ra = hidden units, Rb = tokens, out [T, F] if ep->store_dense.
 hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* Bq, const float* bias, float alpha, int64_t Ra,
-                                   int64_t Rb, int64_t K, uint16_t* out, int64_t ldo, const VnmEpilogue* ep, hipStream_t s);
+                                   int64_t Rb, int64_t K, uint16_t* out, int64_t ldo, const VnmEpilogue* ep, hipStream_t s, const GemmGroup* grp = nullptr);
 // fp8.hip, producers of such operands: quantised copy in the same orientation / transposed; 2:4 pruning that also writes the blocked codes
 // (amax, optional: the tensor's amax slots, see below)
 hipError_t launch_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_blk, hipStream_t s, float* amax = nullptr);
@@ -181,7 +181,7 @@ hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, in
 
 // the same on E4M3 codes (atc: compact transposed codes [F / 2, T], Gq [N, T], both in the blocked pair layout): out = bf16(alpha * sum)
 hipError_t launch_wgrad_vnm_fp8(const uint8_t* atc, const uint8_t* kmask, const uint8_t* Gq, float alpha, int64_t F, int64_t N, int64_t T,
-                                int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
+                                int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 hipError_t launch_wgrad_vnm(const uint16_t* atc, const uint8_t* kmask, const uint16_t* G, int64_t F, int64_t N, int64_t T,
                             int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 

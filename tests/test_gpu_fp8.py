@@ -287,3 +287,42 @@ def test_fp8_step_delayed_scaling_round_trip():
         top = np.abs(fp8.e4m3_decode(s[name].cpu().numpy())).max()
         assert 416.0 <= top <= 448.0, (name, top)              # the largest survivor lands in the top binade (exactly 448 when it is the tensor's maximum)
     assert np.abs(fp8.e4m3_decode(s["y2_codes"].cpu().numpy())).max() == 448.0
+
+
+@pytest.mark.parametrize("wgrad_fp8", [False, True])
+def test_grouped_fp8_step_matches_oracle_per_expert(wgrad_fp8):
+    """The mixture-of-experts form of the fp8 step (uneven segments, one of them empty): every expert's share is checked
+    teacher-forced like the plain fp8 step, with the scales shared by all experts; the empty expert gets zero weight gradients."""
+    from workload import make_moe_inputs
+    D, F = 256, 384
+    m = make_moe_inputs(n_tokens=700, n_experts=3, top_k=2, D=D, F=F, seed=5)
+    seg = np.concatenate([m["seg"][:2], m["seg"][1:]]).astype(np.int64)          # an empty segment in second place
+    extra = make_ffn_inputs(64, D, F, seed=99)
+    W1 = np.concatenate([m["W1"][:1], extra["W1"][None], m["W1"][1:]])
+    W2 = np.concatenate([m["W2"][:1], extra["W2"][None], m["W2"][1:]])
+    b1 = np.concatenate([m["b1"][:1], extra["b1"][None], m["b1"][1:]])
+    mm = dict(X=m["X"], dY=m["dY"], W1=W1, W2=W2, b1=b1)
+    amax = lambda b: float(np.float32(np.abs(oracle.bits_to_f32(b)).max()))
+    sc = dict(x=amax(mm["X"]) / 448, w1=amax(W1) / 448, w2=amax(W2) / 448, y2=20.0 / 448, dy=amax(mm["dY"]) / 448, dy1=30.0 / 448)
+    dev = {k: to_dev(v) for k, v in mm.items()}
+    step = sffn.FfnStepFp8Grouped(seg, D, F, sc, sffn.MODE_SOFT, keep_dense=True, wgrad_fp8=wgrad_fp8)
+    outs = step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    torch.cuda.synchronize()
+    s = {k: (to_bits(v) if v.dtype == torch.bfloat16 else v.cpu().numpy()) for k, v in step.saved().items()}
+    o = {k: to_bits(v) for k, v in zip(("Y3", "dX", "dW1", "dW2"), outs)}
+    assert not o["dW1"][1].any() and not o["dW2"][1].any()
+    y2max = dy1max = 0.0
+    for e in (0, 2, 3):
+        a, b = int(seg[e]), int(seg[e + 1])
+        inp = dict(X=mm["X"][a:b], W1=W1[e], W2=W2[e], b1=b1[e], dY=mm["dY"][a:b])
+        se = {k: s[k][e] for k in ("w1_codes", "w1_meta", "w2t_codes", "w2t_meta")}
+        se.update({k: s[k][a:b] for k in ("y1", "y2_codes", "y2_meta", "dy2", "dy1_vals")})
+        se["colidx"] = s["colidx"][a // 64:b // 64]
+        se["y1_kept"] = s["y1_kept"].reshape(-1)[a * F // 4:b * F // 4]
+        oe = dict(Y3=o["Y3"][a:b], dX=o["dX"][a:b], dW1=o["dW1"][e], dW2=o["dW2"][e])
+        _check_fp8_step_against_oracle(inp, sc, se, oe, sffn.MODE_SOFT, wgrad_fp8)
+        y2max = max(y2max, amax(oracle.sqrelu_vnm_compress(se["y1"])[0]))
+        dy1max = max(dy1max, amax(se["dy1_vals"]))
+    got = step.amax_dict()
+    assert got["x"] == amax(mm["X"]) and got["w1"] == amax(W1) and got["w2"] == amax(W2) and got["dy"] == amax(mm["dY"])
+    assert got["y2"] == y2max and got["dy1"] == dy1max
