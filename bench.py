@@ -337,7 +337,7 @@ def main():
                          % ("ffn_router_step_ref" if args.router else "ffn_sparse_step_ref", Ts, T, Fs, F, " of expert 0" if hw.moe else "", dt)}
 
     # ================= the other configurations, stand-alone kernels, micro-benchmarks =============================
-    configs, kernels, gemm24, venom, router, fp8_bench, wide, router_step, fp8_step = None, None, None, None, None, None, None, None, None
+    configs, kernels, gemm24, venom, router, fp8_bench, wide, router_step, fp8_step, other_mode = None, None, None, None, None, None, None, None, None, None
     if args.headline_only and args.fp8:
         fp8_step = fp8_section(hw, max(3, min(args.steps, 10)), max(1, min(args.warmup, 2)), res["ms_sparse"], res["ms_dense"])
     if not args.headline_only and not args.router and M == 8:
@@ -345,6 +345,16 @@ def main():
         configs = {}
         key = lambda name, zf: "%s@%.2f" % (name, zf)
         configs[key(hw.name, hw.zf)] = dict(head, headline=True)
+        # the other mode of Section 2.2 on the same tensors (the paper's recipe prunes with soft-thresholding; positions, and so every GEMM, are the same)
+        if not hw.moe:
+            other = sffn.MODE_HARD if mode == sffn.MODE_SOFT else sffn.MODE_SOFT
+            alt = sffn.FfnStep(hw.T, hw.D, hw.F, other, M=M)
+            run_alt = lambda: alt(hw.X, hw.W1, hw.W2, hw.b1, hw.dY)
+            for _ in range(ewarm):
+                run_alt()
+            other_mode = {"mode": "hard" if other == sffn.MODE_HARD else "soft", "ms_per_step": round(timed(run_alt, esteps), 4)}
+            del alt
+            free()
         fp8_step = fp8_section(hw, esteps, ewarm, res["ms_sparse"], res["ms_dense"])
         # configs[3]'s sweep of the ReLU zero fraction: same tensors, only the bias shifts
         if hw.name == "70b":
@@ -522,6 +532,7 @@ def main():
         "gemm24_microbench": gemm24,
         "fp8_microbench": fp8_bench,
         "fp8_step": fp8_step,
+        "other_pruning_mode": other_mode,
         "router_conversion": router,
         "roofline": roofline, "cpu_baseline": cpu,
         "paper_context": "paper reports 1.4-1.5x for 2:4 GEMMs and 1.4-1.7x end-to-end on NVIDIA sparse tensor cores (Sections 1, 5.2.3); context, not a target",
