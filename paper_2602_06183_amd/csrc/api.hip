@@ -382,7 +382,7 @@ int vnm_spmm_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* a
 namespace {
 struct Fp8Layout {
     sffn_fp8_ws_layout pub;
-    size_t w1_blk, w2t_blk, xq, xt_blk, dyq, dyt_blk, w2q, w1tq, v24, m24, at_blk, kmask, amax_slots, total;
+    size_t w1_blk, w1_mblk, w2t_blk, w2t_mblk, xq, xt_blk, dyq, dyt_blk, w2q, w1tq, v24, m24, at_blk, kmask, amax_slots, total;
 };
 // E = number of experts (1 for the plain step): weight-shaped tensors hold E matrices back to back
 bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L, int n_experts = 1) {
@@ -399,6 +399,7 @@ bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L, int n_experts = 1) {
     L->pub.dy2 = take(dense ? TF * 2 : 0);
     L->pub.dy1_vals = take(TF / 2);        L->pub.y1_kept = take(TF / 2);
     L->w1_blk = take(F * D / 2);           L->w2t_blk = take(F * D / 2);
+    L->w1_mblk = take(F * D / 8);          L->w2t_mblk = take(F * D / 8);
     L->xq = take(T * D);                   L->xt_blk = take(T * D * 2);
     L->dyq = take(T * D);                  L->dyt_blk = take(T * D * 2);
     L->w2q = take(D * F);                  L->w1tq = take(D * F);
@@ -443,6 +444,7 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     uint8_t *w1c = ws + L.pub.w1_codes, *w1m = ws + L.pub.w1_meta, *w2c = ws + L.pub.w2t_codes, *w2m = ws + L.pub.w2t_meta;
     uint16_t *y1 = (uint16_t*)(ws + L.pub.y1), *dy2 = (uint16_t*)(ws + L.pub.dy2), *dy1v = (uint16_t*)(ws + L.pub.dy1_vals), *ykept = (uint16_t*)(ws + L.pub.y1_kept);
     uint8_t *y2c = ws + L.pub.y2_codes, *y2m = ws + L.pub.y2_meta, *cix = ws + L.pub.colidx;
+    uint8_t *w1mb = ws + L.w1_mblk, *w2mb = ws + L.w2t_mblk;
     uint8_t *w1b = ws + L.w1_blk, *w2b = ws + L.w2t_blk, *xq = ws + L.xq, *dyq = ws + L.dyq, *w2q = ws + L.w2q, *w1tq = ws + L.w1tq;
     uint16_t *xtb = (uint16_t*)(ws + L.xt_blk), *dytb = (uint16_t*)(ws + L.dyt_blk), *atb = (uint16_t*)(ws + L.at_blk);
     uint8_t *v24 = ws + L.v24, *m24 = ws + L.m24, *kmask = ws + L.kmask;
@@ -474,16 +476,16 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     // W1 in one pass per expert: pruned (canonical + blocked codes) for eq. (1), dense and transposed for eq. (7)
     for (int64_t e = 0; e < E; ++e)
         STAGE(launch_transpose_quantize_fp8_blocked(W1 + e * F * D, F, D, D, iw1, w1tq + e * D * F, s, aw1, nullptr, cfg->mode, w1c + e * F * D / 2,
-                                                    w1m + e * F * D / 8, w1b + e * F * D / 2), "step/prune24_fp8(W1)+quantize(W1.T)");
+                                                    w1m + e * F * D / 8, w1b + e * F * D / 2, w1mb + e * F * D / 8), "step/prune24_fp8(W1)+quantize(W1.T)");
     {   // eq. (1) on codes, then eq. (2) + V:N:M compression on the bf16 tile; the survivors leave as codes (and in bf16 for eq. (5))
         VnmEpilogue ep;
         ep.mode = 1; ep.store_dense = keep_dense; ep.vals = (uint16_t*)y2c; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
         ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->y2; ep.at_fp8 = w8; ep.amax = ay2;
-        STAGE(launch_gemm_fp8_blocked(w1b, w1m, xq, b1, sc->x * sc->w1, F, T, D, y1, F, &ep, s, gp), "step/y1+sqrelu_vnm_compress");
+        STAGE(launch_gemm_fp8_blocked(w1b, w1mb, xq, b1, sc->x * sc->w1, F, T, D, y1, F, &ep, s, gp), "step/y1+sqrelu_vnm_compress");
     }
     for (int64_t e = 0; e < E; ++e)
-        STAGE(launch_prune24_fp8_step(W2 + e * D * F, F, D, F, 1, cfg->mode, iw2, w2c + e * F * D / 2, w2m + e * F * D / 8, w2b + e * F * D / 2, s,
-                                      w2q + e * D * F, aw2), "step/prune24_fp8(W2.T)+quantize(W2)");
+        STAGE(launch_prune24_fp8_step(W2 + e * D * F, F, D, F, 1, cfg->mode, iw2, w2c + e * F * D / 2, w2m + e * F * D / 8, w2b + e * F * D / 2,
+                                      w2mb + e * F * D / 8, s, w2q + e * D * F, aw2), "step/prune24_fp8(W2.T)+quantize(W2)");
     STAGE(launch_gemm_fp8_blocked(v24, m24, w2q, nullptr, sc->y2 * sc->w2, T, D, F, Y3, D, nullptr, s, gd), "step/y3");      // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
     if (w8) {
@@ -498,7 +500,7 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
         VnmEpilogue ep;
         ep.mode = 2; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
         ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->dy1; ep.at_fp8 = w8; ep.amax = ady1;
-        STAGE(launch_gemm_fp8_blocked(w2b, w2m, dyq, nullptr, sc->dy * sc->w2, F, T, D, dy2, F, &ep, s, gp), "step/dy2+dsqrelu_vnm");
+        STAGE(launch_gemm_fp8_blocked(w2b, w2mb, dyq, nullptr, sc->dy * sc->w2, F, T, D, dy2, F, &ep, s, gp), "step/dy2+dsqrelu_vnm");
     }
     STAGE(launch_gemm_fp8_blocked(v24, m24, w1tq, nullptr, sc->dy1 * sc->w1, T, D, F, dX, D, nullptr, s, gd), "step/dX");      // eq. (7)
     if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)xtb, sc->dy1 * sc->x, F, D, T, 0, dW1, D, s, gw), "step/dW1");   // eq. (8) on codes

@@ -102,6 +102,13 @@ __host__ __device__ __forceinline__ int64_t mblk_off(int64_t r, int64_t k, int64
     return (((r >> 5) * KS + (k >> 6)) << 8) + (((k >> 4) & 1) << 7) + ((r & 31) << 2) + (((k >> 5) & 1) << 1) + ((k >> 3) & 1);
 }
 
+// The same for fp8 operands (v_smfmac_f32_32x32x64_fp8_fp8 wants a 32-bit index word per lane and 64-k step, no ABID halves): one
+// 512-byte unit per (32 rows, 128 k), row-major inside (16 bytes per row); a wavefront fetches its 32 rows of a stage with two
+// contiguous 4-byte-per-lane loads.  m8blk_off = byte address of the metadata byte covering k..k+7 of row r, KS = K / 128.
+__host__ __device__ __forceinline__ int64_t m8blk_off(int64_t r, int64_t k, int64_t KS) {
+    return (((r >> 5) * KS + (k >> 7)) << 9) + ((r & 31) << 4) + ((k & 127) >> 3);
+}
+
 // Two survivors per 8 columns leave at most two per aligned group of four, so a V:2:8 row block is
 // also two plain 2:4 groups.  Inputs: v = the two survivors (low half first), nib = their positions
 // among the four kept columns, cw = the four kept column offsets (one per byte).  Outputs: the two

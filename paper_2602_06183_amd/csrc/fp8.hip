@@ -82,7 +82,8 @@ __global__ void __launch_bounds__(256) prune24_rows_fp8_kernel(const uint16_t* _
 template <bool SOFT>
 __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* __restrict__ src, int64_t R, int K, int64_t ld, float inv,
                                                               uint8_t* __restrict__ codes, uint8_t* __restrict__ meta, float* __restrict__ amax,
-                                                              uint16_t* __restrict__ codes_blk, uint16_t* __restrict__ src_q_blk, float* __restrict__ amax_src) {
+                                                              uint16_t* __restrict__ codes_blk, uint16_t* __restrict__ src_q_blk, float* __restrict__ amax_src,
+                                                              uint8_t* __restrict__ meta_blk) {
     constexpr int TK = 128, TR = 64, PITCH = TR + 8;
     __shared__ __attribute__((aligned(16))) uint16_t tile[TK * PITCH];
     const int64_t r0 = (int64_t)blockIdx.x * TR;
@@ -124,6 +125,7 @@ __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* _
         *reinterpret_cast<uint4*>(codes + r * (K / 2) + (k0 + 32 * q) / 2) = make_uint4(oc[0], oc[1], oc[2], oc[3]);
         *reinterpret_cast<uint32_t*>(meta + r * (K / 8) + (k0 + 32 * q) / 8) = mbytes;
         if (codes_blk) *reinterpret_cast<uint4*>(codes_blk + blk_off(r, (k0 + 32 * q) / 4, K / 128)) = make_uint4(oc[0], oc[1], oc[2], oc[3]);   // 16 codes = 8 pairs
+        if (meta_blk) *reinterpret_cast<uint32_t*>(meta_blk + m8blk_off(r, k0 + 32 * q, K / 128)) = mbytes;
     }
     note_amax(amax, m);
     if (amax_src) note_amax_slots(amax_src, m_src);      // over every element of the source (its dense use shares the scale)
@@ -278,7 +280,8 @@ __global__ void __launch_bounds__(256) quantize_fp8_blocked_kernel(const uint16_
 template <int EXTRA, bool SOFT>
 __global__ void __launch_bounds__(256) transpose_quantize_fp8_blocked_kernel(const uint16_t* __restrict__ src, int64_t R, int64_t C, int64_t ld, float inv,
                                                                             uint16_t* __restrict__ out, float* __restrict__ amax, uint16_t* __restrict__ out_same,
-                                                                            uint8_t* __restrict__ p_codes, uint8_t* __restrict__ p_meta, uint16_t* __restrict__ p_blk) {
+                                                                            uint8_t* __restrict__ p_codes, uint8_t* __restrict__ p_meta, uint16_t* __restrict__ p_blk,
+                                                                            uint8_t* __restrict__ p_mblk) {
     __shared__ uint16_t tile[64][64 + 2];
     const int tid = threadIdx.x;
     const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
@@ -301,6 +304,7 @@ __global__ void __launch_bounds__(256) transpose_quantize_fp8_blocked_kernel(con
             const int64_t cc = (c0 + seg * 8) / 8;                  // chunk of 8 columns inside the row
             *reinterpret_cast<uint32_t*>(p_codes + (r0 + r) * (C / 2) + cc * 4) = q4;
             p_meta[(r0 + r) * (C / 8) + cc] = (uint8_t)(n0 | (n1 << 4));
+            p_mblk[m8blk_off(r0 + r, cc * 8, C / 128)] = (uint8_t)(n0 | (n1 << 4));
             *reinterpret_cast<uint32_t*>(p_blk + blk_off(r0 + r, cc * 2, C / 128)) = q4;
         }
     }
@@ -347,12 +351,12 @@ hipError_t launch_amax_finish(const float* slots, int n, float* out, hipStream_t
 }
 
 hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s, float* amax,
-                                                 uint8_t* out_same_blk, int prune_mode, uint8_t* p_codes, uint8_t* p_meta, uint8_t* p_blk) {
-    if (C % 64 != 0 || R % 64 != 0 || (out_same_blk && p_codes) || (p_codes && (!p_meta || !p_blk || C % 128 != 0))) return hipErrorInvalidValue;
+                                                 uint8_t* out_same_blk, int prune_mode, uint8_t* p_codes, uint8_t* p_meta, uint8_t* p_blk, uint8_t* p_mblk) {
+    if (C % 64 != 0 || R % 64 != 0 || (out_same_blk && p_codes) || (p_codes && (!p_meta || !p_blk || !p_mblk || C % 128 != 0))) return hipErrorInvalidValue;
     dim3 grid((unsigned)(C / 64), (unsigned)(R / 64));
     uint16_t* o = reinterpret_cast<uint16_t*>(out_t_blk);
 #define SFFN_TQ(E, SOFT) hipLaunchKernelGGL((transpose_quantize_fp8_blocked_kernel<E, SOFT>), grid, dim3(256), 0, s, src, R, C, ld, inv, o, amax, \
-                                           reinterpret_cast<uint16_t*>(out_same_blk), p_codes, p_meta, reinterpret_cast<uint16_t*>(p_blk))
+                                           reinterpret_cast<uint16_t*>(out_same_blk), p_codes, p_meta, reinterpret_cast<uint16_t*>(p_blk), p_mblk)
     if (p_codes) { if (prune_mode == 0) SFFN_TQ(2, false); else SFFN_TQ(2, true); }
     else if (out_same_blk) SFFN_TQ(1, false);
     else SFFN_TQ(0, false);
@@ -367,22 +371,22 @@ hipError_t launch_quantize_fp8(const uint16_t* src, int64_t n, float inv, uint8_
 }
 
 static hipError_t launch_prune24_fp8_impl(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                          float* amax, uint16_t* blk, uint16_t* srcq, float* amax_src, hipStream_t s);
+                                          float* amax, uint16_t* blk, uint16_t* srcq, float* amax_src, uint8_t* mblk, hipStream_t s);
 
 hipError_t launch_prune24_fp8(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
                               float* amax, hipStream_t s) {
-    return launch_prune24_fp8_impl(src, R, K, ld, trans, mode, inv, codes, meta, amax, nullptr, nullptr, nullptr, s);
+    return launch_prune24_fp8_impl(src, R, K, ld, trans, mode, inv, codes, meta, amax, nullptr, nullptr, nullptr, nullptr, s);
 }
 
 hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                   uint8_t* codes_blk, hipStream_t s, uint8_t* src_q_blk, float* amax_src) {
-    if (K % 128 != 0 || (src_q_blk && (!trans || R % 64 != 0 || K % 16 != 0))) return hipErrorInvalidValue;   // a block row holds whole 64-byte pieces of the K / 2 codes per row
+                                   uint8_t* codes_blk, uint8_t* meta_blk, hipStream_t s, uint8_t* src_q_blk, float* amax_src) {
+    if (K % 128 != 0 || !trans || !meta_blk || (src_q_blk && (R % 64 != 0 || K % 16 != 0))) return hipErrorInvalidValue;   // a block row holds whole 64-byte pieces of the K / 2 codes per row
     return launch_prune24_fp8_impl(src, R, K, ld, trans, mode, inv, codes, meta, nullptr, reinterpret_cast<uint16_t*>(codes_blk),
-                                   reinterpret_cast<uint16_t*>(src_q_blk), src_q_blk ? amax_src : nullptr, s);
+                                   reinterpret_cast<uint16_t*>(src_q_blk), src_q_blk ? amax_src : nullptr, meta_blk, s);
 }
 
 static hipError_t launch_prune24_fp8_impl(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                          float* amax, uint16_t* blk, uint16_t* srcq, float* amax_src, hipStream_t s) {
+                                          float* amax, uint16_t* blk, uint16_t* srcq, float* amax_src, uint8_t* mblk, hipStream_t s) {
     if (!trans) {
         const int64_t nchunks = R * (K / 8);
         const unsigned grid = (unsigned)((nchunks + 255) / 256);
@@ -390,8 +394,8 @@ static hipError_t launch_prune24_fp8_impl(const uint16_t* src, int64_t R, int64_
         else           hipLaunchKernelGGL((prune24_rows_fp8_kernel<true>), dim3(grid), dim3(256), 0, s, src, nchunks, (int)(K / 8), ld, inv, codes, meta, amax, blk);
     } else {
         dim3 grid((unsigned)(R / 64), (unsigned)((K + 127) / 128));
-        if (mode == 0) hipLaunchKernelGGL((prune24_cols_fp8_kernel<false>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq, amax_src);
-        else           hipLaunchKernelGGL((prune24_cols_fp8_kernel<true>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq, amax_src);
+        if (mode == 0) hipLaunchKernelGGL((prune24_cols_fp8_kernel<false>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq, amax_src, mblk);
+        else           hipLaunchKernelGGL((prune24_cols_fp8_kernel<true>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq, amax_src, mblk);
     }
     return hipGetLastError();
 }

@@ -16,7 +16,8 @@ namespace sffn {
 namespace {
 
 // FP8 (structured-sparse kernel): both operands are 1-byte E4M3 codes, row-major (stand-alone entry points) or blocked with a pair
-// of codes per 2-byte element (fused fp8 step); the metadata is row-major [R, K/8] in both cases.  In BYTES the tiles are those of
+// of codes per 2-byte element (fused fp8 step); the metadata is row-major [R, K/8] for row-major operands and in 512-byte units
+// (m8blk_off, common.hpp) for blocked ones: 16-byte row pieces fetched one by one cost 17 % of eq. (3) at the 70B-scale layer.  In BYTES the tiles are those of
 // the bf16 kernel (a stage is 128 k instead of 64: 64 survivor bytes per A row, 128 bytes per B row, and the fragment a lane of
 // v_smfmac_f32_32x32x64_fp8_fp8 wants is the same 16 / 2 x 16 bytes), so the kernel runs with K counted in byte pairs and only
 // the metadata differs: 16 survivors per lane and step need a whole 32-bit index word, 16 bytes per row and stage.
@@ -173,6 +174,11 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         a_kstep = blocked ? 1024 : 64;
         b_kstep = blocked ? 1024 * (C::BK / 32) : C::BK * 2;
         m_kstep = (blocked && !FP8) ? 256 : C::META_ROW;
+        if (FP8 && blocked) {       // fp8 metadata units of common.hpp (m8blk_off): 512 contiguous bytes per (32 rows, 128 k), row-major inside
+            m_lane = lane * 4; m_kstep = 512;
+            int gr = i0 + wave * 32; gr = gr < Ra ? gr : Ra - 32;
+            m_base = uniform64(a_meta + (int64_t)(gr >> 5) * (Kld / 64) * 512);
+        }
     }
     // the DMA loads of one stage, issued in two halves (h = 0, 1) so that they can sit between matrix instructions
     auto issue_half = [&](int kt, int stage, int h) {
@@ -196,7 +202,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
             if (SPARSE && !FP8) dma4(m_base, m_lane + (uint32_t)kt * m_kstep, sm + wave * 256);
             if (FP8) {
                 dma4(m_base, m_lane + (uint32_t)kt * m_kstep, sm + wave * 512);
-                dma4(m_base, m_lane + (uint32_t)(16 * (Kld / 4)) + (uint32_t)kt * m_kstep, sm + wave * 512 + 256);
+                // second half of the wave's 32 rows: the next 256 bytes of a blocked unit, or 16 rows further down a row-major array
+                dma4(m_base, m_lane + (blocked ? 256u : (uint32_t)(16 * (Kld / 4))) + (uint32_t)kt * m_kstep, sm + wave * 512 + 256);
             }
         }
     };
@@ -602,9 +609,9 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                 uint32_t* vals_p = reinterpret_cast<uint32_t*>(ep.vals) + ((int64_t)(t0 + (lane >> 3)) * (F / 4) + blk_g * 2) / 2;
                 uint32_t* kept_p = reinterpret_cast<uint32_t*>(ep.ykept) + ykept_off(t0 + (lane >> 3), blk_g, F);
                 uint8_t* meta_p = ep.meta + (int64_t)(t0 + (lane >> 3)) * (F / 16) + (blk_g >> 1);
-                // fp8: v24 holds pairs of codes (4 codes per block = 2 pairs), m24 is row-major [T, F / 8]
+                // fp8: v24 holds pairs of codes (4 codes per block = 2 pairs), m24 is in the fp8 metadata units
                 uint16_t* v24_p = FP8 ? ep.v24 + blk_off(t0 + (lane >> 3), blk_g * 2, F / 128) : ep.v24 + blk_off(t0 + (lane >> 3), blk_g * 4, F / 64);
-                uint8_t* m24_p = FP8 ? ep.m24 + (int64_t)(t0 + (lane >> 3)) * (F / 8) + blk_g : ep.m24 + mblk_off(t0 + (lane >> 3), blk_g * 8, F / 64);
+                uint8_t* m24_p = FP8 ? ep.m24 : ep.m24 + mblk_off(t0 + (lane >> 3), blk_g * 8, F / 64);      // (fp8: address per sweep, below)
                 const uint32_t c0 = (cw & 0xFFu) * 2, c1 = ((cw >> 8) & 0xFFu) * 2, c2 = ((cw >> 16) & 0xFFu) * 2, c3 = (cw >> 24) * 2;
                 uint32_t pre_m[8], pre_y[8];                                // EPI 2: saved metadata and y1 of the 8 sweeps, fetched together
                 if (EPI == 2 && valid) {
@@ -663,7 +670,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                                 *reinterpret_cast<uint32_t*>(v24_p + (int64_t)(it >> 1) * (F / 128) * 512 + (it & 1) * 256) = qa | (qb << 16);
                                 uint32_t m4 = mb8 | (row_shl<1>(mb8) << 8);
                                 m4 |= row_shl<2>(m4) << 16;
-                                if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(m24_p + (int64_t)it * 8 * (F / 8)) = m4;
+                                if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(m24_p + m8blk_off(t0 + t, blk_g * 8, F / 128)) = m4;
                             } else {
                             const uint32_t m2 = mb8 | (row_shl<1>(mb8) << 8);     // two column blocks = 16 k = one lane's half-word of a unit
                             *reinterpret_cast<uint2*>(v24_p + (int64_t)(it >> 1) * (F / 64) * 512 + (it & 1) * 256) = make_uint2(a24, b24);

@@ -36,7 +36,7 @@ struct VnmEpilogue {
     const int32_t* perm = nullptr;
     int logM = 3;
     // fp8 operands (launch_gemm_fp8_blocked, modes 1 / 2): the survivors leave as E4M3 codes quantised with 1 / scale = inv_out: mode 1 writes
-    // vals as codes [T, F / 4] and v24 / m24 as a 2:4 code matrix (v24: pairs of codes in the blocked layout, m24: row-major [T, F / 8]);
+    // vals as codes [T, F / 4] and v24 / m24 as a 2:4 code matrix (v24: pairs of codes in the blocked layout, m24: fp8 metadata units);
     // mode 2 keeps vals = dy1 in bf16 and writes v24 as codes.  ykept, at, kmask, colidx, meta stay as in the bf16 modes.
     float inv_out = 1.0f;
     int at_fp8 = 0;                 // fp8 modes 1 / 2: `at` receives codes (pairs in the blocked layout, [F / 2, T]) instead of bf16
@@ -160,7 +160,7 @@ hipError_t launch_spmm24_fp8(const uint8_t* a_codes, const uint8_t* a_meta, cons
                              int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
 
 // The same contraction on operands in the blocked layout with a pair of codes per 2-byte element (the fused fp8 step): a_codes = packed 2:4
-// codes [Ra, K/2], a_meta row-major [Ra, K/8], Bq = codes [Rb, K].  ep = nullptr: out[i * ldo + j] (eqs. (3), (7): Ra = tokens);
+// codes [Ra, K/2], a_meta in the fp8 metadata units of common.hpp, Bq = codes [Rb, K].  ep = nullptr: out[i * ldo + j] (eqs. (3), (7): Ra = tokens);
 // ep (mode 1 or 2, M = 8): eq. (1) / eq. (4) with the fused V:N:M epilogue, Ra = hidden units, Rb = tokens, out [T, F] if ep->store_dense.
 hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* Bq, const float* bias, float alpha, int64_t Ra,
                                    int64_t Rb, int64_t K, uint16_t* out, int64_t ldo, const VnmEpilogue* ep, hipStream_t s, const GemmGroup* grp = nullptr);
@@ -168,16 +168,16 @@ hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta
 // (amax, optional: the tensor's amax slots, see below)
 hipError_t launch_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_blk, hipStream_t s, float* amax = nullptr);
 // (out_same_blk: also the codes in the source's orientation; p_codes / p_meta / p_blk: also the 2:4 pruning of the rows, mode prune_mode, canonical
-//  codes [R, C/2] + metadata [R, C/8] + blocked codes; at most one of the two extras)
+//  codes [R, C/2] + metadata [R, C/8] + blocked codes + metadata units (p_mblk); at most one of the two extras)
 hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s,
                                                  float* amax = nullptr, uint8_t* out_same_blk = nullptr, int prune_mode = 0, uint8_t* p_codes = nullptr,
-                                                 uint8_t* p_meta = nullptr, uint8_t* p_blk = nullptr);
+                                                 uint8_t* p_meta = nullptr, uint8_t* p_blk = nullptr, uint8_t* p_mblk = nullptr);
 // amax slots of the fused fp8 step: n tensors x 64 slots x 256 bytes (kAmaxSlots, kAmaxSlotStride in common.hpp); the step's kernels take a tensor's slot base
 hipError_t launch_amax_clear(float* slots, int n, hipStream_t s);
 hipError_t launch_amax_finish(const float* slots, int n, float* out, hipStream_t s);
-// (src_q_blk, trans = 1 only: also the unpruned source quantised in its own orientation, [K rows, R codes])
+// (trans = 1 only; meta_blk: the metadata in the fp8 units of common.hpp; src_q_blk: also the unpruned source quantised in its own orientation, [K rows, R codes])
 hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                   uint8_t* codes_blk, hipStream_t s, uint8_t* src_q_blk = nullptr, float* amax_src = nullptr);
+                                   uint8_t* codes_blk, uint8_t* meta_blk, hipStream_t s, uint8_t* src_q_blk = nullptr, float* amax_src = nullptr);
 
 // the same on E4M3 codes (atc: compact transposed codes [F / 2, T], Gq [N, T], both in the blocked pair layout): out = bf16(alpha * sum)
 hipError_t launch_wgrad_vnm_fp8(const uint8_t* atc, const uint8_t* kmask, const uint8_t* Gq, float alpha, int64_t F, int64_t N, int64_t T,
