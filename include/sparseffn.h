@@ -70,6 +70,11 @@ typedef struct sffn_cfg {
  * (4 F / M not a multiple of 64 or above 7168) take it in any case. */
 #define SFFN_FLAG_UNFUSED 2
 #define SFFN_FLAG_FP8_WGRAD 4     /* ffn_sparse_step_fp8 only: eqs. (5), (8) on codes as well */
+/* ffn_sparse_step / ffn_sparse_step_grouped with M = 8: do not write the canonical copies w1_vals / w1_meta, w2t_vals / w2t_meta,
+ * y2_vals and (when eq. (7) does not read it) dy1_vals of sffn_ws_layout.  They are inspection aids: every consumer inside the step
+ * reads its own operand layouts, and Y3, dX, dW1, dW2, y2_meta, colidx, y1_kept are the same bits with or without the flag.  Ignored
+ * for M > 8. */
+#define SFFN_FLAG_LEAN 8
 
 /* Byte offsets, inside the workspace of ffn_sparse_step, of the tensors Alg. 2 line 1 saves
  * from the forward pass and of the other intermediates (all filled when the step returns). */
@@ -197,7 +202,8 @@ int vnm_spmm_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* a
  * dW2 = bf16( (sum_t dec(y2q[t,f]) dec(dYq[t,d])) * (s_y2 s_dy) ), dW1 = bf16( (sum_t dec(dy1q[t,f]) dec(Xq[t,d])) * (s_dy1 s_x) ).
  * amax (device, 6 floats in the order of the scales, or NULL): the step clears it and leaves the largest magnitude of X, W1, W2, y2's
  * survivors, dY and dy1's survivors there (exact maxima; what the caller derives the next step's scales from).
- * Shapes: V = 64, M = 8, T a multiple of 64, D and F multiples of 128; cfg->flags: any of SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD.
+ * Shapes: V = 64, M = 8, T a multiple of 64, D and F multiples of 128; cfg->flags: any of SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD,
+ * SFFN_FLAG_LEAN (the canonical w1 / w2t codes + meta and y2 codes are not written).
  * Workspace: sffn_fp8_workspace_bytes(cfg); after the call it holds, at the offsets of sffn_fp8_workspace_layout: the pruned
  * weights (codes [F, D/2] u8 + meta [F, D/8]), y2 (codes [T, F/4] u8, meta [T, F/16], colidx [T/64, F/8, 4]), dy1 at y2's slots
  * (bf16 [T, F/4]), y1 at y2's slots (y1_kept, runs of 64 tokens x 8 blocks as in ffn_sparse_step) and, with KEEP_DENSE, y1 / dy2. */

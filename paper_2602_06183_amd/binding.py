@@ -186,6 +186,7 @@ def profile_read():
 FLAG_KEEP_DENSE = 1
 FLAG_UNFUSED = 2
 FLAG_FP8_WGRAD = 4
+FLAG_LEAN = 8
 
 
 def dense_sqrelu(y1, out):
@@ -207,8 +208,8 @@ def _cfg(T, D, F, mode=MODE_HARD, V=64, M=8, flags=0):
     return _Cfg(T, D, F, V, M, mode, flags)
 
 
-def _flags(keep_dense, unfused=False):
-    return (FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_UNFUSED if unfused else 0)
+def _flags(keep_dense, unfused=False, lean=False):
+    return (FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_UNFUSED if unfused else 0) | (FLAG_LEAN if lean else 0)
 
 
 def workspace_bytes(T, D, F, mode=MODE_HARD, M=8, keep_dense=False, unfused=False):
@@ -348,12 +349,13 @@ def vnm_wgrad(a_vals, a_meta, a_colidx, G, out_f_major, V=64, M=8):
 class FfnStep:
     """Pre-allocated outputs and workspace for repeated ffn_sparse_step calls on one shape."""
 
-    def __init__(self, T, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8, unfused=False):
+    def __init__(self, T, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8, unfused=False, lean=False):
         """keep_dense: also store the dense y1 and dy2 (SFFN_FLAG_KEEP_DENSE); otherwise only y1 at y2's kept
         slots is saved for the backward pass.  M: V:N:M block width, 8, 16, 32 or 64.  unfused (M >= 16): the path
-        with separate eq. (2) / eq. (6) kernels that always stores y1 and dy2 and produces no y1_kept."""
+        with separate eq. (2) / eq. (6) kernels that always stores y1 and dy2 and produces no y1_kept.  lean (M = 8):
+        the canonical copies of the packed tensors are not written (SFFN_FLAG_LEAN); saved() then holds stale data for them."""
         self.T, self.D, self.F, self.mode, self.keep_dense, self.M = T, D, F, mode, keep_dense, M
-        self.cfg = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused))
+        self.cfg = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused, lean))
         self.layout = workspace_layout(T, D, F, mode, M, keep_dense, unfused)
         self.ws = _u8((self.layout["total"],), device)
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
@@ -397,11 +399,11 @@ class FfnStepGrouped:
     """Pre-allocated outputs and workspace for ffn_sparse_step_grouped: n_experts FFNs, expert e on token rows
     seg[e]..seg[e+1] (host integers, multiples of 64; T = seg[-1])."""
 
-    def __init__(self, seg, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8):
+    def __init__(self, seg, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8, lean=False):
         self.seg = [int(v) for v in seg]
         self.E, self.T, self.D, self.F, self.mode, self.keep_dense, self.M = len(self.seg) - 1, self.seg[-1], D, F, mode, keep_dense, M
         self.seg_c = (ctypes.c_int64 * len(self.seg))(*self.seg)
-        self.cfg = _cfg(self.T, D, F, mode, M=M, flags=FLAG_KEEP_DENSE if keep_dense else 0)
+        self.cfg = _cfg(self.T, D, F, mode, M=M, flags=_flags(keep_dense, False, lean))
         lay = _Layout()
         _check(load().sffn_grouped_workspace_layout(ctypes.byref(self.cfg), self.E, ctypes.byref(lay)))
         self.layout = {n: getattr(lay, n) for n, _ in _Layout._fields_}
@@ -522,10 +524,11 @@ class FfnStepFp8:
     """ffn_sparse_step_fp8 with outputs and workspace allocated once.  scales: dict with the six per-tensor scales
     x, w1, w2, y2, dy, dy1 (positive floats; delayed scaling: the caller derives them from earlier steps)."""
 
-    def __init__(self, T, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False):
-        """wgrad_fp8: eqs. (5), (8) contract codes as well (SFFN_FLAG_FP8_WGRAD); otherwise they are the bf16 contractions."""
+    def __init__(self, T, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False):
+        """wgrad_fp8: eqs. (5), (8) contract codes as well (SFFN_FLAG_FP8_WGRAD); otherwise they are the bf16 contractions.
+        lean: the canonical copies of the packed tensors are not written (SFFN_FLAG_LEAN)."""
         self.T, self.D, self.F, self.mode = T, D, F, mode
-        self.cfg = _cfg(T, D, F, mode, M=8, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0))
+        self.cfg = _cfg(T, D, F, mode, M=8, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0) | (FLAG_LEAN if lean else 0))
         self.scales = _Fp8Scales(*[float(scales[k]) for k in ("x", "w1", "w2", "y2", "dy", "dy1")])
         lay = _Fp8Layout()
         _check(load().sffn_fp8_workspace_layout(ctypes.byref(self.cfg), ctypes.byref(lay)))
@@ -581,11 +584,11 @@ class FfnStepFp8:
 class FfnStepFp8Grouped(FfnStepFp8):
     """ffn_sparse_step_fp8_grouped: n_experts FFNs, expert e on token rows seg[e]..seg[e+1] (host integers, multiples of 64; T = seg[-1])."""
 
-    def __init__(self, seg, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False):
+    def __init__(self, seg, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False):
         self.seg = [int(v) for v in seg]
         self.E, self.T, self.D, self.F, self.mode, self.keep_dense = len(self.seg) - 1, self.seg[-1], D, F, mode, keep_dense
         self.seg_c = (ctypes.c_int64 * len(self.seg))(*self.seg)
-        self.cfg = _cfg(self.T, D, F, mode, M=8, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0))
+        self.cfg = _cfg(self.T, D, F, mode, M=8, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0) | (FLAG_LEAN if lean else 0))
         self.set_scales(scales)
         lay = _Fp8Layout()
         _check(load().sffn_fp8_grouped_workspace_layout(ctypes.byref(self.cfg), self.E, ctypes.byref(lay)))

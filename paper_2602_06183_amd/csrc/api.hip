@@ -387,7 +387,7 @@ struct Fp8Layout {
 // E = number of experts (1 for the plain step): weight-shaped tensors hold E matrices back to back
 bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L, int n_experts = 1) {
     if (!c || !mult64(c->T) || !mult128(c->D) || !mult128(c->F) || c->V != 64 || c->M != 8 || n_experts < 1) return false;
-    if (c->flags & ~(SFFN_FLAG_KEEP_DENSE | SFFN_FLAG_FP8_WGRAD)) return false;
+    if (c->flags & ~(SFFN_FLAG_KEEP_DENSE | SFFN_FLAG_FP8_WGRAD | SFFN_FLAG_LEAN)) return false;
     const bool dense = (c->flags & SFFN_FLAG_KEEP_DENSE) != 0;
     const size_t T = c->T, D = c->D, F = (size_t)c->F * n_experts, TF = T * (size_t)c->F;
     size_t off = 0;
@@ -450,6 +450,7 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     uint8_t *v24 = ws + L.v24, *m24 = ws + L.m24, *kmask = ws + L.kmask;
     const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
     const bool w8 = (cfg->flags & SFFN_FLAG_FP8_WGRAD) != 0;      // eqs. (5), (8) on codes too: X.T, dY.T and the compact transposed survivors as codes
+    if (cfg->flags & SFFN_FLAG_LEAN) { w1c = w1m = w2c = w2m = y2c = nullptr; }     // no canonical copies of the packed tensors (dy1 stays: eq. (8) in bf16 does not need it either, but it is small)
     const float ix = 1.0f / sc->x, iw1 = 1.0f / sc->w1, iw2 = 1.0f / sc->w2, idy = 1.0f / sc->dy;
     // the three ways a token segment meets its expert's weights (see GemmGroup); strides in the units the kernels index: pairs of codes
     GemmGroup g_packed = g, g_dense = g, g_wgrad = g;
@@ -475,8 +476,8 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     }
     // W1 in one pass per expert: pruned (canonical + blocked codes) for eq. (1), dense and transposed for eq. (7)
     for (int64_t e = 0; e < E; ++e)
-        STAGE(launch_transpose_quantize_fp8_blocked(W1 + e * F * D, F, D, D, iw1, w1tq + e * D * F, s, aw1, nullptr, cfg->mode, w1c + e * F * D / 2,
-                                                    w1m + e * F * D / 8, w1b + e * F * D / 2, w1mb + e * F * D / 8), "step/prune24_fp8(W1)+quantize(W1.T)");
+        STAGE(launch_transpose_quantize_fp8_blocked(W1 + e * F * D, F, D, D, iw1, w1tq + e * D * F, s, aw1, nullptr, cfg->mode, w1c ? w1c + e * F * D / 2 : nullptr,
+                                                    w1m ? w1m + e * F * D / 8 : nullptr, w1b + e * F * D / 2, w1mb + e * F * D / 8), "step/prune24_fp8(W1)+quantize(W1.T)");
     {   // eq. (1) on codes, then eq. (2) + V:N:M compression on the bf16 tile; the survivors leave as codes (and in bf16 for eq. (5))
         VnmEpilogue ep;
         ep.mode = 1; ep.store_dense = keep_dense; ep.vals = (uint16_t*)y2c; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
@@ -484,7 +485,7 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
         STAGE(launch_gemm_fp8_blocked(w1b, w1mb, xq, b1, sc->x * sc->w1, F, T, D, y1, F, &ep, s, gp), "step/y1+sqrelu_vnm_compress");
     }
     for (int64_t e = 0; e < E; ++e)
-        STAGE(launch_prune24_fp8_step(W2 + e * D * F, F, D, F, 1, cfg->mode, iw2, w2c + e * F * D / 2, w2m + e * F * D / 8, w2b + e * F * D / 2,
+        STAGE(launch_prune24_fp8_step(W2 + e * D * F, F, D, F, 1, cfg->mode, iw2, w2c ? w2c + e * F * D / 2 : nullptr, w2m ? w2m + e * F * D / 8 : nullptr, w2b + e * F * D / 2,
                                       w2mb + e * F * D / 8, s, w2q + e * D * F, aw2), "step/prune24_fp8(W2.T)+quantize(W2)");
     STAGE(launch_gemm_fp8_blocked(v24, m24, w2q, nullptr, sc->y2 * sc->w2, T, D, F, Y3, D, nullptr, s, gd), "step/y3");      // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
@@ -965,23 +966,26 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     // anyway: X, dY and W1 by the transposes the weight-gradient / input-gradient GEMMs need, W2 by its
     // pruning pass, the activations by the fused epilogues of eqs. (1) and (4).
     // ---- Alg. 1 -------------------------------------------------------------------------------
+    // SFFN_FLAG_LEAN: the canonical copies of the packed tensors (inspection aids: w1 / w2t vals + meta, y2 vals, dy1 vals) are not
+    // written; every consumer inside the step reads the blocked copies, the 2:4 view and the compact transpose anyway
+    const bool lean = (cfg->flags & SFFN_FLAG_LEAN) != 0;
     STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
     // row pruning is per row, so the E stacked [F, D] matrices are one [E * F, D] matrix
-    STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, w1v, w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
+    STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, lean ? nullptr : w1v, lean ? nullptr : w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
     {   // eq. (1), then eq. (2) + V:N:M compression on the tile while it is still in LDS
         VnmEpilogue ep;
-        ep.mode = 1; ep.store_dense = keep_dense; ep.vals = y2v; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
+        ep.mode = 1; ep.store_dense = keep_dense; ep.vals = lean ? nullptr : y2v; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
         ep.v24 = a24v; ep.m24 = a24m; ep.at = atb;
         STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s, gp), "step/y1+sqrelu_vnm_compress");
     }
-    STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, w2v, w2m, w2vb, w2mb, w2b, s, (int)E), "step/prune24(W2.T)");
+    STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, lean ? nullptr : w2v, lean ? nullptr : w2m, w2vb, w2mb, w2b, s, (int)E), "step/prune24(W2.T)");
     STAGE(launch_spmm_blocked(a24v, a24m, w2b, nullptr, T, D, F, 0, Y3, D, s, gd), "step/y3");            // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
     STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
     STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");                          // eq. (5)
     {   // eq. (4), then eq. (6) on y2's kept slots; overwrites the 2:4 view and the transposed tile with dy1's
         VnmEpilogue ep;
-        ep.mode = 2; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
+        ep.mode = 2; ep.store_dense = keep_dense; ep.vals = (lean && !gather_dx) ? nullptr : dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
         ep.v24 = gather_dx ? nullptr : a24v; ep.m24 = a24m; ep.at = atb;
         STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, ep, s, gp), "step/dy2+dsqrelu_vnm");
     }

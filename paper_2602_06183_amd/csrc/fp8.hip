@@ -122,8 +122,10 @@ __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* _
             mbytes |= nib << (4 * g);
         }
         const int64_t r = r0 + rr;
-        *reinterpret_cast<uint4*>(codes + r * (K / 2) + (k0 + 32 * q) / 2) = make_uint4(oc[0], oc[1], oc[2], oc[3]);
-        *reinterpret_cast<uint32_t*>(meta + r * (K / 8) + (k0 + 32 * q) / 8) = mbytes;
+        if (codes) {
+            *reinterpret_cast<uint4*>(codes + r * (K / 2) + (k0 + 32 * q) / 2) = make_uint4(oc[0], oc[1], oc[2], oc[3]);
+            *reinterpret_cast<uint32_t*>(meta + r * (K / 8) + (k0 + 32 * q) / 8) = mbytes;
+        }
         if (codes_blk) *reinterpret_cast<uint4*>(codes_blk + blk_off(r, (k0 + 32 * q) / 4, K / 128)) = make_uint4(oc[0], oc[1], oc[2], oc[3]);   // 16 codes = 8 pairs
         if (meta_blk) *reinterpret_cast<uint32_t*>(meta_blk + m8blk_off(r, k0 + 32 * q, K / 128)) = mbytes;
     }
@@ -302,8 +304,10 @@ __global__ void __launch_bounds__(256) transpose_quantize_fp8_blocked_kernel(con
             select24_f32<SOFT>(w.z & 0xFFFFu, w.z >> 16, w.w & 0xFFFFu, w.w >> 16, n1, d2, e);
             const uint32_t q4 = enc2(a, b, inv) | (enc2(d2, e, inv) << 16);
             const int64_t cc = (c0 + seg * 8) / 8;                  // chunk of 8 columns inside the row
-            *reinterpret_cast<uint32_t*>(p_codes + (r0 + r) * (C / 2) + cc * 4) = q4;
-            p_meta[(r0 + r) * (C / 8) + cc] = (uint8_t)(n0 | (n1 << 4));
+            if (p_codes) {      // (lean form of the step: no canonical copy)
+                *reinterpret_cast<uint32_t*>(p_codes + (r0 + r) * (C / 2) + cc * 4) = q4;
+                p_meta[(r0 + r) * (C / 8) + cc] = (uint8_t)(n0 | (n1 << 4));
+            }
             p_mblk[m8blk_off(r0 + r, cc * 8, C / 128)] = (uint8_t)(n0 | (n1 << 4));
             *reinterpret_cast<uint32_t*>(p_blk + blk_off(r0 + r, cc * 2, C / 128)) = q4;
         }
@@ -352,12 +356,12 @@ hipError_t launch_amax_finish(const float* slots, int n, float* out, hipStream_t
 
 hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s, float* amax,
                                                  uint8_t* out_same_blk, int prune_mode, uint8_t* p_codes, uint8_t* p_meta, uint8_t* p_blk, uint8_t* p_mblk) {
-    if (C % 64 != 0 || R % 64 != 0 || (out_same_blk && p_codes) || (p_codes && (!p_meta || !p_blk || !p_mblk || C % 128 != 0))) return hipErrorInvalidValue;
+    if (C % 64 != 0 || R % 64 != 0 || (out_same_blk && p_blk) || (p_blk && (!p_mblk || C % 128 != 0)) || (p_codes && (!p_meta || !p_blk))) return hipErrorInvalidValue;
     dim3 grid((unsigned)(C / 64), (unsigned)(R / 64));
     uint16_t* o = reinterpret_cast<uint16_t*>(out_t_blk);
 #define SFFN_TQ(E, SOFT) hipLaunchKernelGGL((transpose_quantize_fp8_blocked_kernel<E, SOFT>), grid, dim3(256), 0, s, src, R, C, ld, inv, o, amax, \
                                            reinterpret_cast<uint16_t*>(out_same_blk), p_codes, p_meta, reinterpret_cast<uint16_t*>(p_blk), p_mblk)
-    if (p_codes) { if (prune_mode == 0) SFFN_TQ(2, false); else SFFN_TQ(2, true); }
+    if (p_blk) { if (prune_mode == 0) SFFN_TQ(2, false); else SFFN_TQ(2, true); }
     else if (out_same_blk) SFFN_TQ(1, false);
     else SFFN_TQ(0, false);
 #undef SFFN_TQ

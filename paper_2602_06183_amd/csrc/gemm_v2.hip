@@ -637,9 +637,10 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             const uint32_t p0 = nib & 3u, p1 = nib >> 2;
                             const uint32_t k0 = (p0 == 0) ? y0 : (p0 == 1) ? y1 : y2;
                             const uint32_t k1 = (p1 == 3) ? y3 : (p1 == 2) ? y2 : y1;
-                            if (FP8)    // canonical values are the survivors' codes [T, F / 4]
-                                reinterpret_cast<uint16_t*>(ep.vals)[(int64_t)(t0 + t) * (F / 8) + blk_g] = (uint16_t)fp8_enc2(bf2f(v & 0xFFFFu), bf2f(v >> 16), ep.inv_out);
-                            else
+                            if (FP8) {  // canonical values are the survivors' codes [T, F / 4]
+                                if (ep.vals)
+                                    reinterpret_cast<uint16_t*>(ep.vals)[(int64_t)(t0 + t) * (F / 8) + blk_g] = (uint16_t)fp8_enc2(bf2f(v & 0xFFFFu), bf2f(v >> 16), ep.inv_out);
+                            } else if (ep.vals)       // (lean form: no canonical copy; the 2:4 view and the compact transpose carry the values)
                                 vals_p[(int64_t)it * 8 * (F / 8)] = v;
                             kept_p[it * 64] = k0 | (k1 << 16);
                             // metadata bytes of the row's 8 blocks -> one 32-bit store from the lane of block 0
@@ -657,7 +658,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             const float ya = bf2f(yk & 0xFFFFu), yb = bf2f(yk >> 16);
                             const float ga = 2.0f * d0 * (ya > 0.0f ? ya : 0.0f), gb = 2.0f * d1 * (yb > 0.0f ? yb : 0.0f);
                             v = f2bf2(ga, gb);
-                            vals_p[(int64_t)it * 8 * (F / 8)] = v;
+                            if (ep.vals) vals_p[(int64_t)it * 8 * (F / 8)] = v;
                         }
                         if (FP8) vmax = __builtin_fmaxf(vmax, __builtin_fmaxf(__builtin_fabsf(bf2f(v & 0xFFFFu)), __builtin_fabsf(bf2f(v >> 16))));
                         // the same block as two plain 2:4 groups (blocked operand of eq. (3) / eq. (7))

@@ -53,7 +53,8 @@ __global__ void __launch_bounds__(256) prune24_cols_kernel(const uint16_t* __res
     const int tid = threadIdx.x;
     if (blockIdx.z) {   // batched form: matrix blockIdx.z of a stack of [K, R] sources (ld = R)
         const int64_t m = (int64_t)blockIdx.z * R * K;
-        src += m; vals += m / 2; meta += m / 8;
+        src += m;
+        if (vals) { vals += m / 2; meta += m / 8; }
         if (vblk) { vblk += m / 2; mblk += m / 8; }
         if (src_blk) src_blk += m;
         if (src_t) src_t += m;
@@ -99,10 +100,12 @@ __global__ void __launch_bounds__(256) prune24_cols_kernel(const uint16_t* __res
         mbytes |= nib << (4 * g);
     }
     const int64_t r = r0 + rr;
-    uint16_t* vo = vals + r * (K / 2) + (k0 + 32 * q) / 2;
-    *reinterpret_cast<uint4*>(vo) = make_uint4(ov[0], ov[1], ov[2], ov[3]);
-    *reinterpret_cast<uint4*>(vo + 8) = make_uint4(ov[4], ov[5], ov[6], ov[7]);
-    *reinterpret_cast<uint32_t*>(meta + r * (K / 8) + (k0 + 32 * q) / 8) = mbytes;
+    if (vals) {         // (the fused step's lean form passes no canonical outputs: only the blocked copies are consumed)
+        uint16_t* vo = vals + r * (K / 2) + (k0 + 32 * q) / 2;
+        *reinterpret_cast<uint4*>(vo) = make_uint4(ov[0], ov[1], ov[2], ov[3]);
+        *reinterpret_cast<uint4*>(vo + 8) = make_uint4(ov[4], ov[5], ov[6], ov[7]);
+        *reinterpret_cast<uint32_t*>(meta + r * (K / 8) + (k0 + 32 * q) / 8) = mbytes;
+    }
     if (vblk) {
         uint16_t* vb = vblk + blk_off(r, (k0 + 32 * q) / 2, K / 64);
         *reinterpret_cast<uint4*>(vb) = make_uint4(ov[0], ov[1], ov[2], ov[3]);
@@ -137,8 +140,10 @@ __global__ void __launch_bounds__(256) prune24_rows_step_kernel(const uint16_t* 
     const uint32_t o3 = select24<SOFT>(w1.z & 0xFFFFu, w1.z >> 16, w1.w & 0xFFFFu, w1.w >> 16, n3);
     const uint4 ov = make_uint4(o0, o1, o2, o3);
     const uint16_t mb = (uint16_t)(n0 | (n1 << 4) | (n2 << 8) | (n3 << 12));
-    *reinterpret_cast<uint4*>(vals + r * (K / 2) + k / 2) = ov;
-    *reinterpret_cast<uint16_t*>(meta + r * (K / 8) + k / 8) = mb;
+    if (vals) {
+        *reinterpret_cast<uint4*>(vals + r * (K / 2) + k / 2) = ov;
+        *reinterpret_cast<uint16_t*>(meta + r * (K / 8) + k / 8) = mb;
+    }
     *reinterpret_cast<uint4*>(vblk + blk_off(r, k / 2, K / 64)) = ov;
     *reinterpret_cast<uint16_t*>(mblk + mblk_off(r, k, K / 64)) = mb;
 }

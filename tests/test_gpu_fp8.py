@@ -226,6 +226,10 @@ def test_ffn_sparse_step_fp8(T, D, F, mode, seed, wgrad_fp8):
     amax = lambda b: float(np.float32(np.abs(oracle.bits_to_f32(b)).max()))
     want = dict(x=amax(inp["X"]), w1=amax(inp["W1"]), w2=amax(inp["W2"]), y2=amax(yv), dy=amax(inp["dY"]), dy1=amax(s["dy1_vals"]))
     assert step.amax_dict() == want
+    lean = sffn.FfnStepFp8(T, D, F, sc, mode, wgrad_fp8=wgrad_fp8, lean=True)           # no canonical copies: same outputs
+    for k, v in zip(("Y3", "dX", "dW1", "dW2"), lean(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])):
+        assert np.array_equal(to_bits(v), o[k]), ("lean", k)
+    assert lean.amax_dict() == want
     fast = sffn.FfnStepFp8(T, D, F, sc, mode, wgrad_fp8=wgrad_fp8)
     outs2 = fast(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
     torch.cuda.synchronize()

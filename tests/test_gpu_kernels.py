@@ -642,3 +642,33 @@ def test_ffn_router_step_with_empty_experts():
     one = sffn.FfnRouterStep(T, D, F, M)
     outs_one = [to_bits(t) for t in one.full(dev["means"], dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
     assert all(np.array_equal(a, b) for a, b in zip(outs_one, (Y3, dX, dW1, dW2)))
+
+
+@pytest.mark.parametrize("T,D,F,mode", [(512, 256, 1024, sffn.MODE_HARD), (192, 320, 448, sffn.MODE_SOFT), (128, 128, 14464, sffn.MODE_HARD)])
+def test_lean_step_is_bit_identical(T, D, F, mode):
+    """SFFN_FLAG_LEAN leaves out the canonical copies of the packed tensors and nothing else: the four outputs and what the
+    backward pass needs (metadata, column indices, y1 at the kept slots) are the same bits.  (The third shape takes the
+    2:4-view route for eq. (7), where the canonical dy1 is skipped too.)"""
+    inp = make_ffn_inputs(T, D, F, seed=6)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    full, lean = sffn.FfnStep(T, D, F, mode), sffn.FfnStep(T, D, F, mode, lean=True)
+    lean.ws.fill_(0xA5)
+    a = [to_bits(t).copy() for t in full(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    b = [to_bits(t).copy() for t in lean(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    for name, x, y in zip(("Y3", "dX", "dW1", "dW2"), a, b):
+        assert np.array_equal(x, y), name
+    sa, sb = full.saved(), lean.saved()
+    for k in ("y2_meta", "colidx", "y1_kept"):
+        assert np.array_equal(to_bits(sa[k]), to_bits(sb[k])), k
+    assert np.all(to_bits(sb["w1_vals"]) == 0xA5A5) and np.all(to_bits(sb["y2_vals"]) == 0xA5A5)       # really not written
+
+
+def test_lean_grouped_step_is_bit_identical():
+    D, F = 192, 320
+    m = make_moe_inputs(n_tokens=900, n_experts=4, top_k=2, D=D, F=F, seed=2)
+    dev = {k: to_dev(m[k]) for k in ("X", "W1", "W2", "b1", "dY")}
+    full, lean = sffn.FfnStepGrouped(m["seg"], D, F), sffn.FfnStepGrouped(m["seg"], D, F, lean=True)
+    a = [to_bits(t).copy() for t in full(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    b = [to_bits(t).copy() for t in lean(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    for name, x, y in zip(("Y3", "dX", "dW1", "dW2"), a, b):
+        assert np.array_equal(x, y), name
