@@ -266,6 +266,26 @@ def main():
                                    "tflops_dense_equiv": round(hw.flops / (ms8 * 1e-3) / 1e12, 2)}
                 del st8
                 free()
+            # Table 5's wider blocks with the same operands (fp8 weight gradients): eqs. (3), (7) on the gathered rows of the quantised weights
+            wide8 = {}
+            for m in (16, 32, 64):
+                if hw.moe or (4 * hw.F // m) % 128:
+                    continue
+                first = sffn.FfnStepFp8(hw.T, hw.D, hw.F, sc, mode, M=m)
+                first(hw.X, hw.W1, hw.W2, hw.b1, hw.dY)
+                scm = {k: max(v, 1e-12) / 448 for k, v in first.amax_dict().items()}
+                del first
+                free()
+                st8 = sffn.FfnStepFp8(hw.T, hw.D, hw.F, scm, mode, wgrad_fp8=True, lean=True, M=m)
+                run8 = lambda: st8(hw.X, hw.W1, hw.W2, hw.b1, hw.dY)
+                for _ in range(ewarm):
+                    run8()
+                ms8 = timed(run8, esteps)
+                wide8["64:2:%d" % m] = {"ms_per_step": round(ms8, 4), "speedup_vs_dense_bf16": round(msd / ms8, 4), "tflops_dense_equiv": round(hw.flops / (ms8 * 1e-3) / 1e12, 2)}
+                del st8
+                free()
+            if wide8:
+                fp8_step["wide_blocks_fp8_weight_gradients"] = wide8
         return fp8_step
 
     # ================= headline workload ===========================================================================

@@ -202,11 +202,14 @@ int vnm_spmm_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* a
  * dW2 = bf16( (sum_t dec(y2q[t,f]) dec(dYq[t,d])) * (s_y2 s_dy) ), dW1 = bf16( (sum_t dec(dy1q[t,f]) dec(Xq[t,d])) * (s_dy1 s_x) ).
  * amax (device, 6 floats in the order of the scales, or NULL): the step clears it and leaves the largest magnitude of X, W1, W2, y2's
  * survivors, dY and dy1's survivors there (exact maxima; what the caller derives the next step's scales from).
- * Shapes: V = 64, M = 8, T a multiple of 64, D and F multiples of 128; cfg->flags: any of SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD,
- * SFFN_FLAG_LEAN (the canonical w1 / w2t codes + meta and y2 codes are not written).
+ * Shapes: V = 64, M in {8, 16, 32, 64} (Table 5's blocks), T a multiple of 64, D and F multiples of 128, for M >= 16 also 4 F / M a
+ * multiple of 128 (eqs. (3), (7) then contract only the kept rows of the quantised W2.T / W1, gathered per token block);
+ * cfg->flags: any of SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD, SFFN_FLAG_LEAN (the canonical w1 / w2t codes + meta and, at M = 8, the
+ * y2 codes are not written).
  * Workspace: sffn_fp8_workspace_bytes(cfg); after the call it holds, at the offsets of sffn_fp8_workspace_layout: the pruned
- * weights (codes [F, D/2] u8 + meta [F, D/8]), y2 (codes [T, F/4] u8, meta [T, F/16], colidx [T/64, F/8, 4]), dy1 at y2's slots
- * (bf16 [T, F/4]), y1 at y2's slots (y1_kept, runs of 64 tokens x 8 blocks as in ffn_sparse_step) and, with KEEP_DENSE, y1 / dy2. */
+ * weights (codes [F, D/2] u8 + meta [F, D/8]), y2 (codes [T, 2F/M] u8, meta [T, F/(2M)], colidx [T/64, F/M, 4]), dy1 at y2's slots
+ * (dy1_vals: bf16 [T, F/4] at M = 8, codes [T, 2F/M] u8 at M >= 16), y1 at y2's slots (y1_kept, laid out as in ffn_sparse_step) and,
+ * with KEEP_DENSE, y1 / dy2. */
 typedef struct { float x, w1, w2, y2, dy, dy1; } sffn_fp8_scales;
 typedef struct {
     size_t w1_codes, w1_meta, w2t_codes, w2t_meta, y1, y2_codes, y2_meta, colidx, dy2, dy1_vals, y1_kept, total;

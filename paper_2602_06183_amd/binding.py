@@ -524,11 +524,11 @@ class FfnStepFp8:
     """ffn_sparse_step_fp8 with outputs and workspace allocated once.  scales: dict with the six per-tensor scales
     x, w1, w2, y2, dy, dy1 (positive floats; delayed scaling: the caller derives them from earlier steps)."""
 
-    def __init__(self, T, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False):
+    def __init__(self, T, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False, M=8):
         """wgrad_fp8: eqs. (5), (8) contract codes as well (SFFN_FLAG_FP8_WGRAD); otherwise they are the bf16 contractions.
-        lean: the canonical copies of the packed tensors are not written (SFFN_FLAG_LEAN)."""
-        self.T, self.D, self.F, self.mode = T, D, F, mode
-        self.cfg = _cfg(T, D, F, mode, M=8, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0) | (FLAG_LEAN if lean else 0))
+        lean: the canonical copies of the packed tensors are not written (SFFN_FLAG_LEAN).  M: columns per V:N:M block (8, 16, 32, 64)."""
+        self.T, self.D, self.F, self.mode, self.M = T, D, F, mode, M
+        self.cfg = _cfg(T, D, F, mode, M=M, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0) | (FLAG_LEAN if lean else 0))
         self.scales = _Fp8Scales(*[float(scales[k]) for k in ("x", "w1", "w2", "y2", "dy", "dy1")])
         lay = _Fp8Layout()
         _check(load().sffn_fp8_workspace_layout(ctypes.byref(self.cfg), ctypes.byref(lay)))
@@ -561,7 +561,7 @@ class FfnStepFp8:
 
     def saved(self):
         """Views of what the step leaves in its workspace."""
-        T, D, F, L = self.T, self.D, self.F, self.layout
+        T, D, F, L, M = self.T, self.D, self.F, self.layout, self.M
 
         def view(off, shape, dtype):
             n = 1
@@ -573,9 +573,13 @@ class FfnStepFp8:
         u8 = torch.uint8
         out = dict(w1_codes=view(L["w1_codes"], (F, D // 2), u8), w1_meta=view(L["w1_meta"], (F, D // 8), u8),
                    w2t_codes=view(L["w2t_codes"], (F, D // 2), u8), w2t_meta=view(L["w2t_meta"], (F, D // 8), u8),
-                   y2_codes=view(L["y2_codes"], (T, F // 4), u8), y2_meta=view(L["y2_meta"], (T, F // 16), u8),
-                   colidx=view(L["colidx"], (T // 64, F // 8, 4), u8), dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16),
-                   y1_kept=view(L["y1_kept"], (T, F // 4), torch.bfloat16))
+                   y2_codes=view(L["y2_codes"], (T, 2 * F // M), u8), y2_meta=view(L["y2_meta"], (T, F // (2 * M)), u8),
+                   colidx=view(L["colidx"], (T // 64, F // M, 4), u8), y1_kept=view(L["y1_kept"], (T, 2 * F // M), torch.bfloat16))
+        # dy1's survivors: bf16 at M = 8, codes (the operand of eq. (7) on gathered rows) at M >= 16
+        if M == 8:
+            out["dy1_vals"] = view(L["dy1_vals"], (T, F // 4), torch.bfloat16)
+        else:
+            out["dy1_codes"] = view(L["dy1_vals"], (T, 2 * F // M), u8)
         if self.keep_dense:
             out["y1"], out["dy2"] = view(L["y1"], (T, F), torch.bfloat16), view(L["dy2"], (T, F), torch.bfloat16)
         return out
@@ -584,11 +588,11 @@ class FfnStepFp8:
 class FfnStepFp8Grouped(FfnStepFp8):
     """ffn_sparse_step_fp8_grouped: n_experts FFNs, expert e on token rows seg[e]..seg[e+1] (host integers, multiples of 64; T = seg[-1])."""
 
-    def __init__(self, seg, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False):
+    def __init__(self, seg, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False, M=8):
         self.seg = [int(v) for v in seg]
-        self.E, self.T, self.D, self.F, self.mode, self.keep_dense = len(self.seg) - 1, self.seg[-1], D, F, mode, keep_dense
+        self.E, self.T, self.D, self.F, self.mode, self.keep_dense, self.M = len(self.seg) - 1, self.seg[-1], D, F, mode, keep_dense, M
         self.seg_c = (ctypes.c_int64 * len(self.seg))(*self.seg)
-        self.cfg = _cfg(self.T, D, F, mode, M=8, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0) | (FLAG_LEAN if lean else 0))
+        self.cfg = _cfg(self.T, D, F, mode, M=M, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0) | (FLAG_LEAN if lean else 0))
         self.set_scales(scales)
         lay = _Fp8Layout()
         _check(load().sffn_fp8_grouped_workspace_layout(ctypes.byref(self.cfg), self.E, ctypes.byref(lay)))
@@ -612,7 +616,7 @@ class FfnStepFp8Grouped(FfnStepFp8):
 
     def saved(self):
         """As FfnStepFp8.saved(); weight-shaped tensors carry a leading expert axis."""
-        T, D, F, E, L = self.T, self.D, self.F, self.E, self.layout
+        T, D, F, E, L, M = self.T, self.D, self.F, self.E, self.layout, self.M
 
         def view(off, shape, dtype):
             n = 1
@@ -624,9 +628,13 @@ class FfnStepFp8Grouped(FfnStepFp8):
         u8 = torch.uint8
         out = dict(w1_codes=view(L["w1_codes"], (E, F, D // 2), u8), w1_meta=view(L["w1_meta"], (E, F, D // 8), u8),
                    w2t_codes=view(L["w2t_codes"], (E, F, D // 2), u8), w2t_meta=view(L["w2t_meta"], (E, F, D // 8), u8),
-                   y2_codes=view(L["y2_codes"], (T, F // 4), u8), y2_meta=view(L["y2_meta"], (T, F // 16), u8),
-                   colidx=view(L["colidx"], (T // 64, F // 8, 4), u8), dy1_vals=view(L["dy1_vals"], (T, F // 4), torch.bfloat16),
-                   y1_kept=view(L["y1_kept"], (T, F // 4), torch.bfloat16))
+                   y2_codes=view(L["y2_codes"], (T, 2 * F // M), u8), y2_meta=view(L["y2_meta"], (T, F // (2 * M)), u8),
+                   colidx=view(L["colidx"], (T // 64, F // M, 4), u8), y1_kept=view(L["y1_kept"], (T, 2 * F // M), torch.bfloat16))
+        # dy1's survivors: bf16 at M = 8, codes (the operand of eq. (7) on gathered rows) at M >= 16
+        if M == 8:
+            out["dy1_vals"] = view(L["dy1_vals"], (T, F // 4), torch.bfloat16)
+        else:
+            out["dy1_codes"] = view(L["dy1_vals"], (T, 2 * F // M), u8)
         if self.keep_dense:
             out["y1"], out["dy2"] = view(L["y1"], (T, F), torch.bfloat16), view(L["dy2"], (T, F), torch.bfloat16)
         return out

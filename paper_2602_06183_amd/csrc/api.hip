@@ -386,18 +386,19 @@ struct Fp8Layout {
 };
 // E = number of experts (1 for the plain step): weight-shaped tensors hold E matrices back to back
 bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L, int n_experts = 1) {
-    if (!c || !mult64(c->T) || !mult128(c->D) || !mult128(c->F) || c->V != 64 || c->M != 8 || n_experts < 1) return false;
+    if (!c || !mult64(c->T) || !mult128(c->D) || !mult128(c->F) || c->V != 64 || n_experts < 1) return false;
+    if (c->M != 8 && !(vnm_ok(c->V, c->M) && vnm_spmm_gather_fp8_ok(c->T, c->D, c->F, c->M))) return false;
     if (c->flags & ~(SFFN_FLAG_KEEP_DENSE | SFFN_FLAG_FP8_WGRAD | SFFN_FLAG_LEAN)) return false;
     const bool dense = (c->flags & SFFN_FLAG_KEEP_DENSE) != 0;
-    const size_t T = c->T, D = c->D, F = (size_t)c->F * n_experts, TF = T * (size_t)c->F;
+    const size_t T = c->T, D = c->D, F = (size_t)c->F * n_experts, TF = T * (size_t)c->F, M = (size_t)c->M;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
     L->pub.w1_codes = take(F * D / 2);     L->pub.w1_meta = take(F * D / 8);
     L->pub.w2t_codes = take(F * D / 2);    L->pub.w2t_meta = take(F * D / 8);
     L->pub.y1 = take(dense ? TF * 2 : 0);
-    L->pub.y2_codes = take(TF / 4);        L->pub.y2_meta = take(TF / 16);    L->pub.colidx = take(TF / 64 / 8 * 4);
+    L->pub.y2_codes = take(2 * TF / M);    L->pub.y2_meta = take(TF / (2 * M));    L->pub.colidx = take(TF / 64 / M * 4);
     L->pub.dy2 = take(dense ? TF * 2 : 0);
-    L->pub.dy1_vals = take(TF / 2);        L->pub.y1_kept = take(TF / 2);
+    L->pub.dy1_vals = take(M == 8 ? TF / 2 : 2 * TF / M);        L->pub.y1_kept = take(4 * TF / M);
     L->w1_blk = take(F * D / 2);           L->w2t_blk = take(F * D / 2);
     L->w1_mblk = take(F * D / 8);          L->w2t_mblk = take(F * D / 8);
     L->xq = take(T * D);                   L->xt_blk = take(T * D * 2);
@@ -418,9 +419,10 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     REQUIRE(aligned16(amax), SFFN_EINVAL, "ffn_sparse_step_fp8: amax must be 16-byte aligned");
     Fp8Layout L;
     REQUIRE(n_experts >= 1 && n_experts <= GemmGroup::kMaxExperts, SFFN_EINVAL, "ffn_sparse_step_fp8_grouped: n_experts must be in 1..64");
-    REQUIRE(cfg->M == 8 && cfg->V == 64, SFFN_EUNSUPPORTED, "ffn_sparse_step_fp8: only V = 64, M = 8 is built");
+    REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "ffn_sparse_step_fp8: only V = 64 with M in {8, 16, 32, 64} is built");
     REQUIRE(make_fp8_layout(cfg, &L, n_experts), SFFN_EINVAL,
-            "ffn_sparse_step_fp8: T must be a positive multiple of 64, D and F of 128; flags: SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD");
+            "ffn_sparse_step_fp8: T must be a positive multiple of 64, D and F of 128 (M >= 16: 4 F / M a multiple of 128); flags: "
+            "SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD, SFFN_FLAG_LEAN");
     REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_sparse_step_fp8: unknown mode");
     REQUIRE(X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_sparse_step_fp8: null pointer");
     REQUIRE(aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(dY) && aligned16(Y3) && aligned16(dX) && aligned16(dW1) && aligned16(dW2) &&
@@ -450,7 +452,10 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     uint8_t *v24 = ws + L.v24, *m24 = ws + L.m24, *kmask = ws + L.kmask;
     const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
     const bool w8 = (cfg->flags & SFFN_FLAG_FP8_WGRAD) != 0;      // eqs. (5), (8) on codes too: X.T, dY.T and the compact transposed survivors as codes
-    if (cfg->flags & SFFN_FLAG_LEAN) { w1c = w1m = w2c = w2m = y2c = nullptr; }     // no canonical copies of the packed tensors (dy1 stays: eq. (8) in bf16 does not need it either, but it is small)
+    if (cfg->flags & SFFN_FLAG_LEAN) {      // no canonical copies of the packed tensors (dy1 stays: eq. (8) in bf16 does not need it either, but it is small)
+        w1c = w1m = w2c = w2m = nullptr;
+        if (cfg->M == 8) y2c = nullptr;     // (M >= 16: the gathered-row kernel reads the canonical codes)
+    }
     const float ix = 1.0f / sc->x, iw1 = 1.0f / sc->w1, iw2 = 1.0f / sc->w2, idy = 1.0f / sc->dy;
     // the three ways a token segment meets its expert's weights (see GemmGroup); strides in the units the kernels index: pairs of codes
     GemmGroup g_packed = g, g_dense = g, g_wgrad = g;
@@ -467,6 +472,53 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     float *ax = slot_of(0), *aw1 = slot_of(1), *aw2 = slot_of(2), *ay2 = slot_of(3), *ady = slot_of(4), *ady1 = slot_of(5);
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
     if (amax) STAGE(launch_amax_clear(slots, 6, s), "step/clear(amax)");
+    if (cfg->M != 8) {
+        // Blocks of M = 16, 32, 64 columns (Table 5): the same readings, with the general-M epilogues and eqs. (3), (7) on the kept rows of the
+        // quantised W2.T / W1 (row-major codes, written by the two pruning passes); the survivors are codes in both directions.
+        const int M = cfg->M, logM = M == 16 ? 4 : M == 32 ? 5 : 6;
+        uint8_t *w2tq = w2q, *w1q = w1tq, *dy1c = (uint8_t*)dy1v;       // same sizes as the M = 8 step's dense quantised weights
+        GemmGroup g_rows = g;
+        g_rows.role = 0; g_rows.b_stride = F * D;
+        const GemmGroup* gr = g.n ? &g_rows : nullptr;
+        if (w8) {
+            STAGE(launch_transpose_quantize_fp8_blocked(X, T, D, D, ix, (uint8_t*)xtb, s, ax, xq), "step/quantize(X, X.T)");
+        } else {
+            STAGE(launch_transpose(X, T, D, D, xtb, 1, nullptr, s), "step/X.T");
+            STAGE(launch_quantize_fp8_blocked(X, T, D, D, ix, xq, s, ax), "step/quantize(X)");
+        }
+        for (int64_t e = 0; e < E; ++e)
+            STAGE(launch_prune24_fp8_step(W1 + e * F * D, F, D, D, 0, cfg->mode, iw1, w1c ? w1c + e * F * D / 2 : nullptr, w1m ? w1m + e * F * D / 8 : nullptr,
+                                          w1b + e * F * D / 2, w1mb + e * F * D / 8, s, nullptr, aw1, w1q + e * F * D), "step/prune24_fp8(W1)+quantize(W1)");
+        {
+            VnmEpilogue ep;
+            ep.mode = 5; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = (uint16_t*)y2c; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
+            ep.at = atb; ep.inv_out = 1.0f / sc->y2; ep.at_fp8 = w8; ep.amax = ay2;
+            STAGE(launch_gemm_fp8_blocked(w1b, w1mb, xq, b1, sc->x * sc->w1, F, T, D, y1, F, &ep, s, gp), "step/y1+sqrelu_vnm_compress");
+        }
+        for (int64_t e = 0; e < E; ++e)
+            STAGE(launch_prune24_fp8_step(W2 + e * D * F, F, D, F, 1, cfg->mode, iw2, w2c ? w2c + e * F * D / 2 : nullptr, w2m ? w2m + e * F * D / 8 : nullptr,
+                                          w2b + e * F * D / 2, w2mb + e * F * D / 8, s, nullptr, aw2, w2tq + e * F * D), "step/prune24_fp8(W2.T)+quantize(W2.T)");
+        STAGE(launch_vnm_spmm_gather_fp8(y2c, y2m, cix, w2tq, D, sc->y2 * sc->w2, T, D, F, M, Y3, D, s, gr), "step/y3");                     // eq. (3)
+        if (w8) {
+            STAGE(launch_transpose_quantize_fp8_blocked(dY, T, D, D, idy, (uint8_t*)dytb, s, ady, dyq), "step/quantize(dY, dY.T)");
+        } else {
+            STAGE(launch_transpose(dY, T, D, D, dytb, 1, nullptr, s), "step/dY.T");
+            STAGE(launch_quantize_fp8_blocked(dY, T, D, D, idy, dyq, s, ady), "step/quantize(dY)");
+        }
+        if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)dytb, sc->y2 * sc->dy, F, D, T, 1, dW2, F, s, gw), "step/dW2");
+        else    STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");
+        {
+            VnmEpilogue ep;
+            ep.mode = 6; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = (uint16_t*)dy1c; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
+            ep.at = atb; ep.inv_out = 1.0f / sc->dy1; ep.at_fp8 = w8; ep.amax = ady1;
+            STAGE(launch_gemm_fp8_blocked(w2b, w2mb, dyq, nullptr, sc->dy * sc->w2, F, T, D, dy2, F, &ep, s, gp), "step/dy2+dsqrelu_vnm");
+        }
+        STAGE(launch_vnm_spmm_gather_fp8(dy1c, y2m, cix, w1q, D, sc->dy1 * sc->w1, T, D, F, M, dX, D, s, gr), "step/dX");                   // eq. (7)
+        if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)xtb, sc->dy1 * sc->x, F, D, T, 0, dW1, D, s, gw), "step/dW1");
+        else    STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");
+        if (amax) STAGE(launch_amax_finish(slots, 6, amax, s), "step/finish(amax)");
+        return SFFN_OK;
+    }
     // ---- Alg. 1 -------------------------------------------------------------------------------
     if (w8) {       // X.T codes for eq. (8) and X codes for eq. (1) in one pass over X
         STAGE(launch_transpose_quantize_fp8_blocked(X, T, D, D, ix, (uint8_t*)xtb, s, ax, xq), "step/quantize(X, X.T)");

@@ -59,23 +59,36 @@ __global__ void __launch_bounds__(256) quantize_fp8_kernel(const uint4* __restri
 template <bool SOFT>
 __global__ void __launch_bounds__(256) prune24_rows_fp8_kernel(const uint16_t* __restrict__ src, int64_t nchunks, int cpr, int64_t ld, float inv,
                                                               uint8_t* __restrict__ codes, uint8_t* __restrict__ meta, float* __restrict__ amax,
-                                                              uint16_t* __restrict__ codes_blk) {
+                                                              uint16_t* __restrict__ codes_blk, uint8_t* __restrict__ meta_blk, uint8_t* __restrict__ src_q,
+                                                              float* __restrict__ amax_src) {
     const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    float m = 0.0f;
+    float m = 0.0f, m_src = 0.0f;
     if (c < nchunks) {
         const int64_t r = c / cpr;
         const uint4 w = *reinterpret_cast<const uint4*>(src + r * ld + (c - r * cpr) * 8);
+        if (src_q) {        // the unpruned source itself, quantised, row-major [R, K] codes (its dense use shares the scale)
+            const float f[8] = {bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16),
+                                bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16)};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) m_src = __builtin_fmaxf(m_src, __builtin_fabsf(f[e]));
+            *reinterpret_cast<uint2*>(src_q + c * 8) =
+                make_uint2(enc2(f[0], f[1], inv) | (enc2(f[2], f[3], inv) << 16), enc2(f[4], f[5], inv) | (enc2(f[6], f[7], inv) << 16));
+        }
         uint32_t n0, n1;
         float a, b, d, e;
         select24_f32<SOFT>(w.x & 0xFFFFu, w.x >> 16, w.y & 0xFFFFu, w.y >> 16, n0, a, b);
         select24_f32<SOFT>(w.z & 0xFFFFu, w.z >> 16, w.w & 0xFFFFu, w.w >> 16, n1, d, e);
         m = __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(a), __builtin_fabsf(b)), __builtin_fmaxf(__builtin_fabsf(d), __builtin_fabsf(e)));
         const uint32_t q4 = enc2(a, b, inv) | (enc2(d, e, inv) << 16);
-        *reinterpret_cast<uint32_t*>(codes + c * 4) = q4;
-        meta[c] = (uint8_t)(n0 | (n1 << 4));
+        if (codes) {
+            *reinterpret_cast<uint32_t*>(codes + c * 4) = q4;
+            meta[c] = (uint8_t)(n0 | (n1 << 4));
+        }
         if (codes_blk) *reinterpret_cast<uint32_t*>(codes_blk + blk_off(r, (c - r * cpr) * 2, cpr / 16)) = q4;   // 4 codes = pairs 2 c', 2 c' + 1; K / 2 bytes per row
+        if (meta_blk) meta_blk[m8blk_off(r, (c - r * cpr) * 8, cpr / 16)] = (uint8_t)(n0 | (n1 << 4));
     }
     note_amax(amax, m);
+    if (amax_src) note_amax_slots(amax_src, m_src);
 }
 
 // groups run along the strided axis: S[r, k] = src[k * ld + r]; a workgroup takes 64 logical rows x 128 k through LDS
@@ -83,7 +96,7 @@ template <bool SOFT>
 __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* __restrict__ src, int64_t R, int K, int64_t ld, float inv,
                                                               uint8_t* __restrict__ codes, uint8_t* __restrict__ meta, float* __restrict__ amax,
                                                               uint16_t* __restrict__ codes_blk, uint16_t* __restrict__ src_q_blk, float* __restrict__ amax_src,
-                                                              uint8_t* __restrict__ meta_blk) {
+                                                              uint8_t* __restrict__ meta_blk, uint8_t* __restrict__ s_q) {
     constexpr int TK = 128, TR = 64, PITCH = TR + 8;
     __shared__ __attribute__((aligned(16))) uint16_t tile[TK * PITCH];
     const int64_t r0 = (int64_t)blockIdx.x * TR;
@@ -96,6 +109,12 @@ __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* _
         uint4 w = make_uint4(0, 0, 0, 0);
         if (k0 + kk < K) w = *reinterpret_cast<const uint4*>(src + (int64_t)(k0 + kk) * ld + r0 + seg * 8);
         *reinterpret_cast<uint4*>(&tile[kk * PITCH + seg * 8]) = w;
+        if (s_q && !src_q_blk && amax_src) {    // (the magnitudes of the source, when only its transposed copy is written below)
+            m_src = __builtin_fmaxf(m_src, __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(bf2f(w.x & 0x7FFFu)), __builtin_fabsf(bf2f((w.x >> 16) & 0x7FFFu))),
+                                                            __builtin_fmaxf(__builtin_fabsf(bf2f(w.y & 0x7FFFu)), __builtin_fabsf(bf2f((w.y >> 16) & 0x7FFFu)))));
+            m_src = __builtin_fmaxf(m_src, __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(bf2f(w.z & 0x7FFFu)), __builtin_fabsf(bf2f((w.z >> 16) & 0x7FFFu))),
+                                                            __builtin_fmaxf(__builtin_fabsf(bf2f(w.w & 0x7FFFu)), __builtin_fabsf(bf2f((w.w >> 16) & 0x7FFFu)))));
+        }
         if (src_q_blk && k0 + kk < K) {    // the unpruned source itself, quantised, in its own orientation [K rows, R codes] (blocked pairs)
             const float f[8] = {bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16),
                                 bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16)};
@@ -109,13 +128,14 @@ __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* _
     const int rr = tid % 64, q = tid / 64;
     float m = 0.0f;
     if (k0 + 32 * q < K) {
-        uint32_t oc[4], mbytes = 0;
+        uint32_t oc[4], mbytes = 0, sq[8];
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
             const uint16_t* p = &tile[(32 * q + 4 * g) * PITCH + rr];
             uint32_t nib;
             float a, b;
             select24_f32<SOFT>(p[0], p[PITCH], p[2 * PITCH], p[3 * PITCH], nib, a, b);
+            if (s_q) sq[g] = enc2(bf2f(p[0]), bf2f(p[PITCH]), inv) | (enc2(bf2f(p[2 * PITCH]), bf2f(p[3 * PITCH]), inv) << 16);
             m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(a), __builtin_fabsf(b)));
             const uint32_t c2 = enc2(a, b, inv);
             if (g & 1) oc[g >> 1] |= c2 << 16; else oc[g >> 1] = c2;
@@ -128,6 +148,11 @@ __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* _
         }
         if (codes_blk) *reinterpret_cast<uint4*>(codes_blk + blk_off(r, (k0 + 32 * q) / 4, K / 128)) = make_uint4(oc[0], oc[1], oc[2], oc[3]);   // 16 codes = 8 pairs
         if (meta_blk) *reinterpret_cast<uint32_t*>(meta_blk + m8blk_off(r, k0 + 32 * q, K / 128)) = mbytes;
+        if (s_q) {          // the unpruned logical matrix S itself, quantised, row-major [R, K] codes (rows of it are gathered by eq. (3) for M >= 16)
+            uint4* d = reinterpret_cast<uint4*>(s_q + r * K + k0 + 32 * q);
+            d[0] = make_uint4(sq[0], sq[1], sq[2], sq[3]);
+            d[1] = make_uint4(sq[4], sq[5], sq[6], sq[7]);
+        }
     }
     note_amax(amax, m);
     if (amax_src) note_amax_slots(amax_src, m_src);      // over every element of the source (its dense use shares the scale)
@@ -375,7 +400,7 @@ hipError_t launch_quantize_fp8(const uint16_t* src, int64_t n, float inv, uint8_
 }
 
 static hipError_t launch_prune24_fp8_impl(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                          float* amax, uint16_t* blk, uint16_t* srcq, float* amax_src, uint8_t* mblk, hipStream_t s);
+                                          float* amax, uint16_t* blk, uint16_t* srcq, float* amax_src, uint8_t* mblk, hipStream_t s, uint8_t* s_q = nullptr);
 
 hipError_t launch_prune24_fp8(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
                               float* amax, hipStream_t s) {
@@ -383,23 +408,23 @@ hipError_t launch_prune24_fp8(const uint16_t* src, int64_t R, int64_t K, int64_t
 }
 
 hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                   uint8_t* codes_blk, uint8_t* meta_blk, hipStream_t s, uint8_t* src_q_blk, float* amax_src) {
-    if (K % 128 != 0 || !trans || !meta_blk || (src_q_blk && (R % 64 != 0 || K % 16 != 0))) return hipErrorInvalidValue;   // a block row holds whole 64-byte pieces of the K / 2 codes per row
+                                   uint8_t* codes_blk, uint8_t* meta_blk, hipStream_t s, uint8_t* src_q_blk, float* amax_src, uint8_t* s_q) {
+    if (K % 128 != 0 || !meta_blk || (src_q_blk && (!trans || R % 64 != 0 || K % 16 != 0)) || (src_q_blk && s_q)) return hipErrorInvalidValue;   // a block row holds whole 64-byte pieces of the K / 2 codes per row
     return launch_prune24_fp8_impl(src, R, K, ld, trans, mode, inv, codes, meta, nullptr, reinterpret_cast<uint16_t*>(codes_blk),
-                                   reinterpret_cast<uint16_t*>(src_q_blk), src_q_blk ? amax_src : nullptr, meta_blk, s);
+                                   reinterpret_cast<uint16_t*>(src_q_blk), (src_q_blk || s_q) ? amax_src : nullptr, meta_blk, s, s_q);
 }
 
 static hipError_t launch_prune24_fp8_impl(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                          float* amax, uint16_t* blk, uint16_t* srcq, float* amax_src, uint8_t* mblk, hipStream_t s) {
+                                          float* amax, uint16_t* blk, uint16_t* srcq, float* amax_src, uint8_t* mblk, hipStream_t s, uint8_t* s_q) {
     if (!trans) {
         const int64_t nchunks = R * (K / 8);
         const unsigned grid = (unsigned)((nchunks + 255) / 256);
-        if (mode == 0) hipLaunchKernelGGL((prune24_rows_fp8_kernel<false>), dim3(grid), dim3(256), 0, s, src, nchunks, (int)(K / 8), ld, inv, codes, meta, amax, blk);
-        else           hipLaunchKernelGGL((prune24_rows_fp8_kernel<true>), dim3(grid), dim3(256), 0, s, src, nchunks, (int)(K / 8), ld, inv, codes, meta, amax, blk);
+        if (mode == 0) hipLaunchKernelGGL((prune24_rows_fp8_kernel<false>), dim3(grid), dim3(256), 0, s, src, nchunks, (int)(K / 8), ld, inv, codes, meta, amax, blk, mblk, s_q, amax_src);
+        else           hipLaunchKernelGGL((prune24_rows_fp8_kernel<true>), dim3(grid), dim3(256), 0, s, src, nchunks, (int)(K / 8), ld, inv, codes, meta, amax, blk, mblk, s_q, amax_src);
     } else {
         dim3 grid((unsigned)(R / 64), (unsigned)((K + 127) / 128));
-        if (mode == 0) hipLaunchKernelGGL((prune24_cols_fp8_kernel<false>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq, amax_src, mblk);
-        else           hipLaunchKernelGGL((prune24_cols_fp8_kernel<true>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq, amax_src, mblk);
+        if (mode == 0) hipLaunchKernelGGL((prune24_cols_fp8_kernel<false>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq, amax_src, mblk, s_q);
+        else           hipLaunchKernelGGL((prune24_cols_fp8_kernel<true>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq, amax_src, mblk, s_q);
     }
     return hipGetLastError();
 }

@@ -59,7 +59,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
     constexpr bool GEN_F = EPI >= 16 && EPI < 32, GEN_B = EPI >= 32;
     constexpr int LOGM = (GEN_F || GEN_B) ? (EPI & 15) : 3;
     static_assert(!(GEN_F || GEN_B) || (LOGM >= 4 && LOGM <= 6), "wide V:N:M blocks: M = 16, 32 or 64");
-    static_assert(!FP8 || (SPARSE && (EPI == 0 || (BLOCKED && (EPI == 1 || EPI == 2)))), "fp8 operands: structured-sparse kernel; fused epilogues for M = 8 only");
+    static_assert(!FP8 || (SPARSE && (EPI == 0 || (BLOCKED && (EPI == 1 || EPI == 2 || GEN_F || GEN_B)))), "fp8 operands: structured-sparse kernel; the step's fused epilogues");
     constexpr bool blocked = BLOCKED;       // operands in the blocked layout of common.hpp (fused step) or row-major (stand-alone entry points)
     using C = Cfg<SPARSE, FP8>;
     constexpr int BM = C::BM, BN = C::BN, WM = 128, WN = 64, FM = 4, FN = 2;
@@ -506,7 +506,10 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                 }
                 const uint32_t q0 = (cb & 0xFFu) * 2, q1 = ((cb >> 8) & 0xFFu) * 2, q2 = ((cb >> 16) & 0xFFu) * 2, q3 = (cb >> 24) * 2;
                 const int r_lane = lane >> (6 - LOGM);                    // token of sweep 0; sweep s adds s * M
+                // survivors of (token, block): a pair of bf16, or (fp8 operands) a pair of codes
                 uint32_t* vals_p = reinterpret_cast<uint32_t*>(ep.vals) + (int64_t)(t0 + r_lane) * (F >> LOGM) + blk0 + b;
+                uint16_t* codes_p = ep.vals + (int64_t)(t0 + r_lane) * (F >> LOGM) + blk0 + b;
+                float vmax = 0.0f;                                        // fp8: largest survivor magnitude of this half tile
                 uint32_t* kept_p = reinterpret_cast<uint32_t*>(ep.ykept) + ((((int64_t)(t0 >> 6) * (F >> 6) + (f0 >> 6)) << 6) + r_lane) * NB + b;
                 uint8_t* meta_p = ep.meta + (int64_t)(t0 + r_lane) * (F >> (LOGM + 1)) + ((blk0 + b) >> 1);
                 uint32_t pre_m[NB], pre_y[NB];
@@ -532,7 +535,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             const uint32_t p0 = nib & 3u, p1 = nib >> 2;
                             const uint32_t k0 = (p0 == 0) ? y0 : (p0 == 1) ? y1 : y2;
                             const uint32_t k1 = (p1 == 3) ? y3 : (p1 == 2) ? y2 : y1;
-                            vals_p[(int64_t)sw * M * (F >> LOGM)] = v;
+                            if (FP8) codes_p[(int64_t)sw * M * (F >> LOGM)] = (uint16_t)fp8_enc2(bf2f(v & 0xFFFFu), bf2f(v >> 16), ep.inv_out);
+                            else vals_p[(int64_t)sw * M * (F >> LOGM)] = v;
                             kept_p[sw * M * NB] = k0 | (k1 << 16);
                             // two blocks share a metadata byte: neighbours in the lane order (M = 16, 32) or the two halves of the wave tile (M = 64)
                             if (LOGM == 4) {
@@ -554,8 +558,10 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             const float d1 = bf2f(*reinterpret_cast<const uint16_t*>(row + o1 * 2));
                             const float ya = bf2f(yk & 0xFFFFu), yb = bf2f(yk >> 16);
                             v = f2bf2(2.0f * d0 * (ya > 0.0f ? ya : 0.0f), 2.0f * d1 * (yb > 0.0f ? yb : 0.0f));
-                            vals_p[(int64_t)sw * M * (F >> LOGM)] = v;
+                            if (FP8) codes_p[(int64_t)sw * M * (F >> LOGM)] = (uint16_t)fp8_enc2(bf2f(v & 0xFFFFu), bf2f(v >> 16), ep.inv_out);
+                            else vals_p[(int64_t)sw * M * (F >> LOGM)] = v;
                         }
+                        if (FP8) vmax = __builtin_fmaxf(vmax, __builtin_fmaxf(__builtin_fabsf(bf2f(v & 0xFFFFu)), __builtin_fabsf(bf2f(v >> 16))));
                         // compact row of a survivor at column o of the block: group (b M + o) / 8 of the half tile, position = kept columns of
                         // that group below o
                         const uint32_t o0 = (cb >> (8 * (nib & 3u))) & 0xFFu, o1 = (cb >> (8 * (nib >> 2))) & 0xFFu;
@@ -566,12 +572,20 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         *reinterpret_cast<uint16_t*>(ttile + r1 * EP + t * 2) = (uint16_t)(v >> 16);
                     }
                 }
+                if (FP8 && ep.amax) note_amax_slots(ep.amax, vmax);
                 wave_lds_sync();
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {          // 2 groups of 16 compact rows x 2 chunks of 32 tokens, 1 KB each
                     const int fr = (q >> 1) * 16 + (lane >> 2), tc = (q & 1) * 32 + (lane & 3) * 8;
-                    if (valid)
-                        *reinterpret_cast<uint4*>(ep.at + blk_off(f0 / 2 + fr, t0 + tc, tok_ld / 32)) = *reinterpret_cast<const uint4*>(ttile + fr * EP + tc * 2);
+                    const uint4 w = *reinterpret_cast<const uint4*>(ttile + fr * EP + tc * 2);
+                    if (FP8 && ep.at_fp8) {     // fp8 weight gradients: codes, as in the M = 8 epilogues below
+                        if (valid)
+                            *reinterpret_cast<uint2*>(ep.at + blk_off(f0 / 2 + fr, (t0 + tc) / 2, tok_ld / 64)) =
+                                make_uint2(fp8_enc2(bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), ep.inv_out) | (fp8_enc2(bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16), ep.inv_out) << 16),
+                                           fp8_enc2(bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), ep.inv_out) | (fp8_enc2(bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16), ep.inv_out) << 16));
+                    } else if (valid) {
+                        *reinterpret_cast<uint4*>(ep.at + blk_off(f0 / 2 + fr, t0 + tc, tok_ld / 32)) = w;
+                    }
                 }
             }
             if (EPI == 1 || EPI == 2) {
@@ -792,7 +806,8 @@ hipError_t launch_spmm24_fp8(const uint8_t* a_codes, const uint8_t* a_meta, cons
 
 hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* Bq, const float* bias, float alpha, int64_t Ra,
                                    int64_t Rb, int64_t K, uint16_t* out, int64_t ldo, const VnmEpilogue* ep, hipStream_t s, const GemmGroup* grp) {
-    if (K % 128 != 0 || (ep && ep->mode != 1 && ep->mode != 2)) return hipErrorInvalidValue;
+    if (K % 128 != 0 || (ep && ep->mode != 1 && ep->mode != 2 && ep->mode != 5 && ep->mode != 6)) return hipErrorInvalidValue;
+    if (ep && ep->mode >= 5 && (ep->logM < 4 || ep->logM > 6)) return hipErrorInvalidValue;
     const int tiles_m = (int)((Ra + 255) / 256), tiles_n = (int)((Rb + 255) / 256);
     const VnmEpilogue e = ep ? *ep : VnmEpilogue();
     const GemmGroup g = grp ? *grp : GemmGroup();
@@ -807,7 +822,9 @@ hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta
                                               (int)(K / 2), out, ldo, tiles_m, tiles_n, e, g, alpha)
     if (!ep) SFFN_F8(false, 0);
     else if (ep->mode == 1) SFFN_F8(true, 1);
-    else SFFN_F8(true, 2);
+    else if (ep->mode == 2) SFFN_F8(true, 2);
+    else if (ep->mode == 5) { if (ep->logM == 4) SFFN_F8(true, 20); else if (ep->logM == 5) SFFN_F8(true, 21); else SFFN_F8(true, 22); }
+    else                    { if (ep->logM == 4) SFFN_F8(true, 36); else if (ep->logM == 5) SFFN_F8(true, 37); else SFFN_F8(true, 38); }
 #undef SFFN_F8
     return hipGetLastError();
 }

@@ -38,6 +38,7 @@ struct VnmEpilogue {
     // fp8 operands (launch_gemm_fp8_blocked, modes 1 / 2): the survivors leave as E4M3 codes quantised with 1 / scale = inv_out: mode 1 writes
     // vals as codes [T, F / 4] and v24 / m24 as a 2:4 code matrix (v24: pairs of codes in the blocked layout, m24: fp8 metadata units);
     // mode 2 keeps vals = dy1 in bf16 and writes v24 as codes.  ykept, at, kmask, colidx, meta stay as in the bf16 modes.
+    // fp8 modes 5 / 6: vals = the survivors' codes [T, 2 F / M] in both directions (the operand of the gathered-row kernel); the rest as above.
     float inv_out = 1.0f;
     int at_fp8 = 0;                 // fp8 modes 1 / 2: `at` receives codes (pairs in the blocked layout, [F / 2, T]) instead of bf16
     float* amax = nullptr;          // fp8 modes 1 / 2: amax slots for the survivors' magnitudes (y2 / dy1)
@@ -95,6 +96,11 @@ bool vnm_spmm_gather_ok(int64_t T, int64_t N, int64_t F, int M);
 // grp (role 0, host segment table): the token blocks of segment e take expert e's matrix Wk + e * b_stride.
 hipError_t launch_vnm_spmm_gather(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* colidx, const uint16_t* Wk, int64_t ldw,
                                   int64_t T, int64_t N, int64_t F, int M, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
+// The same on E4M3 codes: a_codes [T, 2 F / M] + the same metadata and column offsets, Wq = codes [F, ldw bytes], out = bf16(alpha * sum);
+// 4 F / M a multiple of 128; b_stride of grp in bytes.
+bool vnm_spmm_gather_fp8_ok(int64_t T, int64_t N, int64_t F, int M);
+hipError_t launch_vnm_spmm_gather_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* colidx, const uint8_t* Wq, int64_t ldw, float alpha,
+                                      int64_t T, int64_t N, int64_t F, int M, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 hipError_t launch_vnm_to_24(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
                             uint16_t* vals24, uint8_t* meta24, hipStream_t s);
 hipError_t launch_vnm_expand_t(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
@@ -161,7 +167,8 @@ hipError_t launch_spmm24_fp8(const uint8_t* a_codes, const uint8_t* a_meta, cons
 
 // The same contraction on operands in the blocked layout with a pair of codes per 2-byte element (the fused fp8 step): a_codes = packed 2:4
 // codes [Ra, K/2], a_meta in the fp8 metadata units of common.hpp, Bq = codes [Rb, K].  ep = nullptr: out[i * ldo + j] (eqs. (3), (7): Ra = tokens);
-// ep (mode 1 or 2, M = 8): eq. (1) / eq. (4) with the fused V:N:M epilogue, Ra = hidden units, Rb = tokens, out [T, F] if ep->store_dense.
+// ep (mode 1 or 2: M = 8; mode 5 or 6: M = 2^logM = 16, 32, 64): eq. (1) / eq. (4) with the fused V:N:M epilogue, Ra = hidden units, Rb = tokens,
+// out [T, F] if ep->store_dense.
 hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* Bq, const float* bias, float alpha, int64_t Ra,
                                    int64_t Rb, int64_t K, uint16_t* out, int64_t ldo, const VnmEpilogue* ep, hipStream_t s, const GemmGroup* grp = nullptr);
 // fp8.hip, producers of such operands: quantised copy in the same orientation / transposed; 2:4 pruning that also writes the blocked codes
@@ -175,9 +182,12 @@ hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R,
 // amax slots of the fused fp8 step: n tensors x 64 slots x 256 bytes (kAmaxSlots, kAmaxSlotStride in common.hpp); the step's kernels take a tensor's slot base
 hipError_t launch_amax_clear(float* slots, int n, hipStream_t s);
 hipError_t launch_amax_finish(const float* slots, int n, float* out, hipStream_t s);
-// (trans = 1 only; meta_blk: the metadata in the fp8 units of common.hpp; src_q_blk: also the unpruned source quantised in its own orientation, [K rows, R codes])
+// (meta_blk: the metadata in the fp8 units of common.hpp; src_q_blk, trans = 1 only: also the unpruned source quantised in its own orientation,
+//  [K rows, R codes], blocked; s_q: also the unpruned logical matrix [R, K] quantised, row-major codes (the gathered operand of eqs. (3), (7)
+//  for M >= 16); amax_src: amax slots of the unpruned tensor; codes / meta may be null)
 hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                   uint8_t* codes_blk, uint8_t* meta_blk, hipStream_t s, uint8_t* src_q_blk = nullptr, float* amax_src = nullptr);
+                                   uint8_t* codes_blk, uint8_t* meta_blk, hipStream_t s, uint8_t* src_q_blk = nullptr, float* amax_src = nullptr,
+                                   uint8_t* s_q = nullptr);
 
 // the same on E4M3 codes (atc: compact transposed codes [F / 2, T], Gq [N, T], both in the blocked pair layout): out = bf16(alpha * sum)
 hipError_t launch_wgrad_vnm_fp8(const uint8_t* atc, const uint8_t* kmask, const uint8_t* Gq, float alpha, int64_t F, int64_t N, int64_t T,

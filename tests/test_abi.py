@@ -74,7 +74,9 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     assert lib.ffn_sparse_step_fp8(ctypes.byref(cfg), None, *args, fake, 1 << 40, None, None) == -1                 # no scales
     assert lib.ffn_sparse_step_fp8(ctypes.byref(cfg), ctypes.byref(sc), *args, fake, 16, None, None) == -3          # workspace too small
     assert lib.ffn_sparse_step_fp8(ctypes.byref(binding._Cfg(512, 192, 1024, 64, 8, 0, 0)), ctypes.byref(sc), *args, fake, 1 << 40, None, None) == -1   # D % 128
-    assert lib.ffn_sparse_step_fp8(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 16, 0, 0)), ctypes.byref(sc), *args, fake, 1 << 40, None, None) == -2  # M = 16
+    assert lib.ffn_sparse_step_fp8(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 12, 0, 0)), ctypes.byref(sc), *args, fake, 1 << 40, None, None) == -2  # M = 12
+    assert lib.ffn_sparse_step_fp8(ctypes.byref(binding._Cfg(512, 256, 1280, 64, 64, 0, 0)), ctypes.byref(sc), *args, fake, 1 << 40, None, None) == -1  # 4 F / M = 80
+    assert lib.ffn_sparse_step_fp8(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 16, 0, 0)), ctypes.byref(sc), *args, fake, 16, None, None) == -3       # M = 16: workspace
     assert lib.ffn_sparse_step_fp8(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 8, 0, 2)), ctypes.byref(sc), *args, fake, 1 << 40, None, None) == -1   # unknown flag
     zero = binding._Fp8Scales(1.0, 1.0, 0.0, 1.0, 1.0, 1.0)
     assert lib.ffn_sparse_step_fp8(ctypes.byref(cfg), ctypes.byref(zero), *args, fake, 1 << 40, None, None) == -1 and b"scales" in lib.sffn_last_error()

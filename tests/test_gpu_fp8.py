@@ -171,39 +171,45 @@ def _fp8_step_scales(inp):
                 dy=amax(inp["dY"]) / 448, dy1=max(amax(ref["dy1_vals"]), 1e-6) / 448)
 
 
-def _check_fp8_step_against_oracle(inp, sc, s, outs, mode, wgrad_fp8=False):
-    """Teacher-forced: every oracle stage consumes the GPU's output of the stage before it."""
+def _check_fp8_step_against_oracle(inp, sc, s, outs, mode, wgrad_fp8=False, M=8):
+    """Teacher-forced: every oracle stage consumes the GPU's output of the stage before it.  Returns dy1's survivors (bf16 bits)."""
     f8 = oracle.fp8
     T, F = s["y1"].shape
     c1, m1 = f8.prune24_compress_fp8(inp["W1"], sc["w1"], mode)
     assert np.array_equal(s["w1_meta"], m1) and np.array_equal(s["w1_codes"], c1)
     xq = f8.quantize_fp8(inp["X"], sc["x"])
     assert_gemm_close(s["y1"], f8.spmm24_fp8(xq, sc["x"], c1, m1, sc["w1"], inp["b1"]), "y1")
-    yc, ym, cix = f8.sqrelu_vnm_compress_fp8(s["y1"], sc["y2"])
+    yc, ym, cix = f8.sqrelu_vnm_compress_fp8(s["y1"], sc["y2"], 64, M)
     assert np.array_equal(s["colidx"], cix) and np.array_equal(s["y2_meta"], ym) and np.array_equal(s["y2_codes"], yc)
-    yv, ym_b, cix_b = oracle.sqrelu_vnm_compress(s["y1"])                 # the bf16 survivors (weight gradients, y1_kept)
+    yv, ym_b, cix_b = oracle.sqrelu_vnm_compress(s["y1"], 64, M)          # the bf16 survivors (weight gradients, y1_kept)
     assert np.array_equal(ym_b, ym) and np.array_equal(cix_b, cix)
-    ones = np.arange(1, yv.size + 1, dtype=np.uint32).reshape(yv.shape)
-    slot_of = oracle.vnm_decompress((ones & 0xFFFF).astype(np.uint16), ym, cix).astype(np.int64) \
-        + (oracle.vnm_decompress((ones >> 16).astype(np.uint16), ym, cix).astype(np.int64) << 16)
-    want_kept = np.zeros(yv.size, dtype=np.uint16)
-    tt, ff = np.nonzero(slot_of)
-    want_kept[slot_of[tt, ff] - 1] = s["y1"][tt, ff]
-    want_kept = want_kept.reshape(T // 64, 64, F // 64, 8, 2).transpose(0, 2, 1, 3, 4)
-    assert np.array_equal(s["y1_kept"].reshape(-1), want_kept.reshape(-1))
-    assert_gemm_close(outs["Y3"], f8.vnm_spmm_fp8(yc, ym, cix, sc["y2"], f8.quantize_fp8(inp["W2"], sc["w2"]), sc["w2"], 0), "y3")
+    if M == 8:
+        ones = np.arange(1, yv.size + 1, dtype=np.uint32).reshape(yv.shape)
+        slot_of = oracle.vnm_decompress((ones & 0xFFFF).astype(np.uint16), ym, cix).astype(np.int64) \
+            + (oracle.vnm_decompress((ones >> 16).astype(np.uint16), ym, cix).astype(np.int64) << 16)
+        want_kept = np.zeros(yv.size, dtype=np.uint16)
+        tt, ff = np.nonzero(slot_of)
+        want_kept[slot_of[tt, ff] - 1] = s["y1"][tt, ff]
+        want_kept = want_kept.reshape(T // 64, 64, F // 64, 8, 2).transpose(0, 2, 1, 3, 4)
+        assert np.array_equal(s["y1_kept"].reshape(-1), want_kept.reshape(-1))
+    assert_gemm_close(outs["Y3"], f8.vnm_spmm_fp8(yc, ym, cix, sc["y2"], f8.quantize_fp8(inp["W2"], sc["w2"]), sc["w2"], 0, 64, M), "y3")
     c2, m2 = f8.prune24_compress_fp8(np.ascontiguousarray(inp["W2"].T), sc["w2"], mode)
     assert np.array_equal(s["w2t_meta"], m2) and np.array_equal(s["w2t_codes"], c2)
     assert_gemm_close(s["dy2"], f8.spmm24_fp8(f8.quantize_fp8(inp["dY"], sc["dy"]), sc["dy"], c2, m2, sc["w2"], None), "dy2")
-    dv = oracle.dsqrelu_vnm(s["dy2"], s["y1"], ym, cix)
-    assert np.array_equal(s["dy1_vals"], dv)
-    assert_gemm_close(outs["dX"], f8.vnm_spmm_fp8(f8.quantize_fp8(dv, sc["dy1"]), ym, cix, sc["dy1"], f8.quantize_fp8(inp["W1"], sc["w1"]), sc["w1"], 1), "dX")
+    dv = oracle.dsqrelu_vnm(s["dy2"], s["y1"], ym, cix, 64, M)
+    dq = f8.quantize_fp8(dv, sc["dy1"])
+    if M == 8:
+        assert np.array_equal(s["dy1_vals"], dv)
+    else:           # wide blocks: dy1's survivors leave as codes only (y1 at the kept slots is checked through them)
+        assert np.array_equal(s["dy1_codes"], dq)
+    assert_gemm_close(outs["dX"], f8.vnm_spmm_fp8(dq, ym, cix, sc["dy1"], f8.quantize_fp8(inp["W1"], sc["w1"]), sc["w1"], 1, 64, M), "dX")
     if wgrad_fp8:
-        assert_gemm_close(outs["dW2"], f8.vnm_wgrad_fp8(yc, ym, cix, sc["y2"], f8.quantize_fp8(inp["dY"], sc["dy"]), sc["dy"], 0), "dW2")
-        assert_gemm_close(outs["dW1"], f8.vnm_wgrad_fp8(f8.quantize_fp8(dv, sc["dy1"]), ym, cix, sc["dy1"], xq, sc["x"], 1), "dW1")
+        assert_gemm_close(outs["dW2"], f8.vnm_wgrad_fp8(yc, ym, cix, sc["y2"], f8.quantize_fp8(inp["dY"], sc["dy"]), sc["dy"], 0, 64, M), "dW2")
+        assert_gemm_close(outs["dW1"], f8.vnm_wgrad_fp8(dq, ym, cix, sc["dy1"], xq, sc["x"], 1, 64, M), "dW1")
     else:
-        assert_gemm_close(outs["dW2"], oracle.vnm_wgrad(yv, ym, cix, inp["dY"], 0), "dW2")
-        assert_gemm_close(outs["dW1"], oracle.vnm_wgrad(dv, ym, cix, inp["X"], 1), "dW1")
+        assert_gemm_close(outs["dW2"], oracle.vnm_wgrad(yv, ym, cix, inp["dY"], 0, 64, M), "dW2")
+        assert_gemm_close(outs["dW1"], oracle.vnm_wgrad(dv, ym, cix, inp["X"], 1, 64, M), "dW1")
+    return dv
 
 
 @pytest.mark.parametrize("wgrad_fp8", [False, True])
@@ -244,10 +250,80 @@ def test_ffn_sparse_step_fp8(T, D, F, mode, seed, wgrad_fp8):
     assert np.array_equal(to_bits(s2["dy1_vals"]), s["dy1_vals"]) and np.array_equal(to_bits(s2["y1_kept"]), s["y1_kept"])
 
 
+@pytest.mark.parametrize("wgrad_fp8", [False, True])
+@pytest.mark.parametrize("M,T,D,F,mode,seed", [(16, 192, 256, 512, sffn.MODE_HARD, 0), (32, 192, 256, 1024, sffn.MODE_SOFT, 1), (64, 256, 384, 2048, sffn.MODE_HARD, 2),
+                                               (16, 512, 256, 1536, sffn.MODE_SOFT, 3), (64, 128, 128, 6144, sffn.MODE_HARD, 4)])
+def test_ffn_sparse_step_fp8_wide_blocks(M, T, D, F, mode, seed, wgrad_fp8):
+    """The fp8 step with V:2:M blocks of 16 / 32 / 64 columns (Table 5): general-M epilogues on codes, eqs. (3), (7) on the gathered rows of
+    the quantised weights.  Teacher-forced stage by stage; then the timed configurations must give the same bits."""
+    from workload import make_ffn_inputs
+    inp = make_ffn_inputs(T, D, F, seed=seed)
+    sc = _fp8_step_scales(inp)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    step = sffn.FfnStepFp8(T, D, F, sc, mode, keep_dense=True, wgrad_fp8=wgrad_fp8, M=M)
+    outs = step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    torch.cuda.synchronize()
+    s = {k: to_bits(v) if v.dtype == torch.bfloat16 else v.cpu().numpy() for k, v in step.saved().items()}
+    o = {k: to_bits(v) for k, v in zip(("Y3", "dX", "dW1", "dW2"), outs)}
+    dv = _check_fp8_step_against_oracle(inp, sc, s, o, mode, wgrad_fp8, M)
+    density = np.mean(oracle.vnm_decompress(oracle.fp8.codes_as_bf16_bits(s["y2_codes"]), s["y2_meta"], s["colidx"], 64, M) != 0)
+    assert density <= 2.0 / M + 1e-9                       # Table 5: sparsity at least 1 - N / M
+    yv = oracle.sqrelu_vnm_compress(s["y1"], 64, M)[0]
+    amax = lambda b: float(np.float32(np.abs(oracle.bits_to_f32(b)).max()))
+    want = dict(x=amax(inp["X"]), w1=amax(inp["W1"]), w2=amax(inp["W2"]), y2=amax(yv), dy=amax(inp["dY"]), dy1=amax(dv))
+    assert step.amax_dict() == want
+    for kw in (dict(lean=True), dict()):
+        other = sffn.FfnStepFp8(T, D, F, sc, mode, wgrad_fp8=wgrad_fp8, M=M, **kw)
+        for k, v in zip(("Y3", "dX", "dW1", "dW2"), other(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])):
+            assert np.array_equal(to_bits(v), o[k]), (kw, k)
+        assert other.amax_dict() == want
+        s2 = other.saved()
+        for k in ("y2_codes", "y2_meta", "colidx", "dy1_codes"):
+            assert np.array_equal(s2[k].cpu().numpy(), s[k]), (kw, k)
+
+
+def test_grouped_fp8_step_wide_blocks_matches_oracle_per_expert():
+    """The grouped fp8 step at M = 32 (uneven segments, one of them empty), every expert's share teacher-forced like the plain step."""
+    from workload import make_moe_inputs
+    D, F, M = 256, 1024, 32
+    m = make_moe_inputs(n_tokens=600, n_experts=3, top_k=2, D=D, F=F, seed=6)
+    seg = np.concatenate([m["seg"][:1], m["seg"][:1], m["seg"][1:]]).astype(np.int64)          # an empty segment in first place
+    extra = make_ffn_inputs(64, D, F, seed=98)
+    W1 = np.concatenate([extra["W1"][None], m["W1"]])
+    W2 = np.concatenate([extra["W2"][None], m["W2"]])
+    b1 = np.concatenate([extra["b1"][None], m["b1"]])
+    mm = dict(X=m["X"], dY=m["dY"], W1=W1, W2=W2, b1=b1)
+    amax = lambda b: float(np.float32(np.abs(oracle.bits_to_f32(b)).max()))
+    sc = dict(x=amax(mm["X"]) / 448, w1=amax(W1) / 448, w2=amax(W2) / 448, y2=20.0 / 448, dy=amax(mm["dY"]) / 448, dy1=30.0 / 448)
+    dev = {k: to_dev(v) for k, v in mm.items()}
+    step = sffn.FfnStepFp8Grouped(seg, D, F, sc, sffn.MODE_HARD, keep_dense=True, wgrad_fp8=True, M=M)
+    outs = step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    torch.cuda.synchronize()
+    s = {k: (to_bits(v) if v.dtype == torch.bfloat16 else v.cpu().numpy()) for k, v in step.saved().items()}
+    o = {k: to_bits(v) for k, v in zip(("Y3", "dX", "dW1", "dW2"), outs)}
+    assert not o["dW1"][0].any() and not o["dW2"][0].any()
+    y2max = dy1max = 0.0
+    for e in (1, 2, 3):
+        a, b = int(seg[e]), int(seg[e + 1])
+        inp = dict(X=mm["X"][a:b], W1=W1[e], W2=W2[e], b1=b1[e], dY=mm["dY"][a:b])
+        se = {k: s[k][e] for k in ("w1_codes", "w1_meta", "w2t_codes", "w2t_meta")}
+        se.update({k: s[k][a:b] for k in ("y1", "y2_codes", "y2_meta", "dy2", "dy1_codes")})
+        se["colidx"] = s["colidx"][a // 64:b // 64]
+        oe = dict(Y3=o["Y3"][a:b], dX=o["dX"][a:b], dW1=o["dW1"][e], dW2=o["dW2"][e])
+        dv = _check_fp8_step_against_oracle(inp, sc, se, oe, sffn.MODE_HARD, True, M)
+        y2max = max(y2max, amax(oracle.sqrelu_vnm_compress(se["y1"], 64, M)[0]))
+        dy1max = max(dy1max, amax(dv))
+    got = step.amax_dict()
+    assert got["x"] == amax(mm["X"]) and got["w1"] == amax(W1) and got["w2"] == amax(W2) and got["dy"] == amax(mm["dY"])
+    assert got["y2"] == y2max and got["dy1"] == dy1max
+
+
 def test_ffn_sparse_step_fp8_rejects_what_it_does_not_cover():
     from paper_2602_06183_amd import binding
     with pytest.raises(sffn.SffnError):
         sffn.FfnStepFp8(64, 64, 128, dict(x=1, w1=1, w2=1, y2=1, dy=1, dy1=1))               # D not a multiple of 128
+    with pytest.raises(sffn.SffnError):
+        sffn.FfnStepFp8(64, 128, 1280, dict(x=1, w1=1, w2=1, y2=1, dy=1, dy1=1), M=64)       # 4 F / M = 80 is not a multiple of 128
     step = sffn.FfnStepFp8(64, 128, 128, dict(x=1, w1=1, w2=1, y2=0.0, dy=1, dy1=1))
     z = lambda *shape: torch.zeros(shape, dtype=torch.bfloat16, device="cuda")
     with pytest.raises(sffn.SffnError):
