@@ -386,3 +386,63 @@ def test_full_size_fp8_step(wgrad_fp8):
         dense_dy1 = oracle.vnm_decompress(s["dy1_vals"], s["y2_meta"], s["colidx"])[:, cols]
         want = oracle.dense_nt(np.ascontiguousarray(dense_dy1.T), np.ascontiguousarray(inp["X"].T))
         assert_gemm_close(dW1[cols], want, "dW1")
+
+
+@pytest.mark.parametrize("M", [16, 64])
+def test_full_size_fp8_step_wide_blocks(M):
+    """ffn_sparse_step_fp8 with blocks of 16 / 64 columns at the 7B layer in the timed configuration (fp8 weight gradients, no canonical copies
+    of the packed weights): the packed activation bit-consistent with the oracle's compressor on sampled token blocks, eqs. (3), (7) on those
+    blocks and eqs. (5), (8) on sampled hidden units against the oracle's fp8 contractions, teacher-forced on the GPU's packed operands."""
+    from oracle import fp8 as f8
+    T, D, F = CONFIGS["7b"]
+    inp = make_ffn_inputs(T, D, F, seed=0)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    amax = lambda t: float(t.float().abs().max())
+    sc = dict(x=amax(dev["X"]) / 448, w1=amax(dev["W1"]) / 448, w2=amax(dev["W2"]) / 448, y2=1.0, dy=amax(dev["dY"]) / 448, dy1=1.0)
+    first = sffn.FfnStepFp8(T, D, F, sc, M=M)                       # the delayed-scaling loop: one call to learn the inner tensors' maxima
+    first(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    sc = {k: v / 448 for k, v in first.amax_dict().items()}
+    del first
+    step = sffn.FfnStepFp8(T, D, F, sc, wgrad_fp8=True, lean=True, M=M)
+    Y3, dX, dW1, dW2 = (to_bits(t) for t in step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"]))
+    s = {k: (to_bits(v) if v.dtype == torch.bfloat16 else v.cpu().numpy()) for k, v in step.saved().items()}
+    rng = np.random.default_rng(M)
+    rows = (np.sort(rng.choice(T // 64, 3, replace=False))[:, None] * 64 + np.arange(64)[None, :]).reshape(-1)      # three whole token blocks
+    c1, m1 = f8.prune24_compress_fp8(inp["W1"], sc["w1"])
+    xq = f8.quantize_fp8(inp["X"], sc["x"])
+    y1_ref = f8.spmm24_fp8(xq[rows], sc["x"], c1, m1, sc["w1"], inp["b1"])
+    yc, ym, cix = s["y2_codes"][rows], s["y2_meta"][rows], s["colidx"][rows[::64] // 64]
+    # the column choice follows the GPU's own y1, which differs from the reference y1 by rounding: the kept columns' scores must be within
+    # that rounding of the four largest, and the codes must decode to y2 of the reference y1 within fp8 spacing
+    y2_ref = oracle.bits_to_f32(oracle.sqrelu(y1_ref))
+    got = oracle.bits_to_f32(oracle.vnm_decompress(f8.codes_as_bf16_bits(yc), ym, cix, 64, M)) * np.float32(sc["y2"])
+    nz = got != 0
+    assert 0.2 / M < nz.mean() <= 2.0 / M
+    assert np.all(np.abs(got[nz] - y2_ref[nz]) <= (2.0 ** -4 + 2.0 ** -6) * np.abs(y2_ref[nz]) + 2.0 ** -9 * sc["y2"])
+    score = y2_ref.reshape(3, 64, F // M, M).sum(axis=1)                                  # [block of tokens, column block, column]
+    kept = np.take_along_axis(score, cix.astype(np.int64), axis=2)
+    fourth = -np.sort(-score, axis=2)[:, :, 3:4]
+    assert np.all(kept >= fourth * (1 - 2.0 ** -6) - 1e-6)
+    w2q = f8.quantize_fp8(inp["W2"], sc["w2"])
+    assert_gemm_close(Y3[rows], f8.vnm_spmm_fp8(yc, ym, cix, sc["y2"], w2q, sc["w2"], 0, 64, M), "y3")
+    dq = s["dy1_codes"]
+    w1q = f8.quantize_fp8(inp["W1"], sc["w1"])
+    assert_gemm_close(dX[rows], f8.vnm_spmm_fp8(dq[rows], ym, cix, sc["dy1"], w1q, sc["w1"], 1, 64, M), "dX")
+    del w1q, w2q, c1, m1
+    # weight gradients on codes for sampled blocks of hidden units, over all tokens
+    cols = (np.sort(rng.choice(F // M, 2, replace=False))[:, None] * M + np.arange(M)[None, :]).reshape(-1)
+    sub = lambda codes: oracle.vnm_decompress(np.ascontiguousarray(codes.reshape(T, F // M, 2)[:, cols[::M] // M].reshape(T, -1)),
+                                              np.ascontiguousarray(_meta_cols(s["y2_meta"], cols[::M] // M)),
+                                              np.ascontiguousarray(s["colidx"][:, cols[::M] // M]), 64, M)
+    d1 = f8.e4m3_decode(sub(dq)).astype(np.float64)
+    want = d1.T @ f8.e4m3_decode(xq).astype(np.float64) * np.float64(np.float32(sc["dy1"]) * np.float32(sc["x"]))
+    assert_gemm_close(dW1[cols], oracle.f64_to_bits(want), "dW1")
+    y2d = f8.e4m3_decode(sub(s["y2_codes"])).astype(np.float64)
+    want = f8.e4m3_decode(f8.quantize_fp8(inp["dY"], sc["dy"])).astype(np.float64).T @ y2d * np.float64(np.float32(sc["y2"]) * np.float32(sc["dy"]))
+    assert_gemm_close(dW2[:, cols], oracle.f64_to_bits(want), "dW2")
+
+
+def _meta_cols(meta, blocks):
+    """The metadata nibbles of the given column blocks, repacked two per byte ([T, len(blocks) / 2])."""
+    nib = np.stack([meta & 0xF, meta >> 4], axis=-1).reshape(meta.shape[0], -1)[:, blocks]
+    return (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)

@@ -78,10 +78,10 @@ def test_router_full_step_replays_in_a_graph(M):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("wgrad_fp8", [False, True])
-def test_fp8_step_replays_in_a_graph(wgrad_fp8):
-    T, D, F = 256, 256, 512
+@pytest.mark.parametrize("wgrad_fp8,M", [(False, 8), (True, 8), (True, 16), (False, 64)])
+def test_fp8_step_replays_in_a_graph(wgrad_fp8, M):
+    T, D, F = 256, 256, 512 if M < 64 else 2048
     sc = dict(x=4.5 / 448, w1=0.1 / 448, w2=0.1 / 448, y2=2.0 / 448, dy=4.5 / 448, dy1=4.0 / 448)
-    a, b = sffn.FfnStepFp8(T, D, F, sc, wgrad_fp8=wgrad_fp8), sffn.FfnStepFp8(T, D, F, sc, wgrad_fp8=wgrad_fp8)
+    a, b = sffn.FfnStepFp8(T, D, F, sc, wgrad_fp8=wgrad_fp8, M=M), sffn.FfnStepFp8(T, D, F, sc, wgrad_fp8=wgrad_fp8, M=M)
     call = lambda step: (lambda d: step(d["X"], d["W1"], d["W2"], d["b1"], d["dY"]))
     _replay_against_eager(lambda seed: make_ffn_inputs(T, D, F, seed=seed), call(a), call(b), ("X", "W1", "W2", "b1", "dY"))
