@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparseffn.so")
-SOURCES = ["api.hip", "prune24.hip", "vnm.hip", "vnm_general.hip", "gemm_v2.hip", "gemm_wgrad.hip", "gemm_gather.hip", "router.hip", "dense_ref.hip", "noalloc.hip", "fp8.hip"]
+SOURCES = ["api.hip", "prune24.hip", "vnm.hip", "vnm_general.hip", "gemm_v2.hip", "gemm_wgrad.hip", "gemm_gather.hip", "gemm_vnm8.hip", "router.hip", "dense_ref.hip", "noalloc.hip", "fp8.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-inline-asm"]
 

@@ -893,6 +893,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
             "ffn_sparse_step: T must be below 65536 and F * n_experts below 2^31");
     REQUIRE(workspace && ws_bytes >= L.total, SFFN_EWORKSPACE, "ffn_sparse_step: workspace missing or too small");
     const int64_t T = cfg->T, D = cfg->D, F = cfg->F, E = n_experts;
+    REQUIRE(cfg->M != 8 || F * D * 2 < ((int64_t)1 << 32), SFFN_EUNSUPPORTED, "ffn_sparse_step: a weight matrix must stay below 4 GiB");
     GemmGroup g;                                    // g.n = 0: plain step
     if (seg) {
         REQUIRE(seg[0] == 0 && seg[E] == T, SFFN_EINVAL, "ffn_sparse_step_grouped: seg_offsets must start at 0 and end at T");
@@ -1010,44 +1011,44 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     const GemmGroup* gd = g.n ? &g_dense : nullptr;
     const GemmGroup* gw = g.n ? &g_wgrad : nullptr;
 
-    // eq. (7) on the gathered-row kernel when it covers the shape: W1 is already contraction-major, so its transpose and
-    // the plain-2:4 view of dy1 are not needed (measured 0.015 ms per step faster at the 1B shape)
-    const bool gather_dx = g.n == 0 && vnm_spmm_gather_ok(T, D, F, 8) && F * D * 2 < ((int64_t)1 << 32);
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
-    // Every GEMM operand is first brought into the blocked layout by the kernel that reads or produces it
-    // anyway: X, dY and W1 by the transposes the weight-gradient / input-gradient GEMMs need, W2 by its
-    // pruning pass, the activations by the fused epilogues of eqs. (1) and (4).
+    // Every GEMM operand is first brought into the layout its kernel reads by the pass that reads or produces it anyway: X and dY
+    // by the transposes the weight-gradient GEMMs need, the pruned weights by their pruning passes (W2's also writes the unpruned
+    // W2.T, contraction-major, for eq. (3)), the activations by the fused epilogues of eqs. (1) and (4).  Eqs. (3), (7) contract the
+    // V:2:8 activation as it is (gemm_vnm8.hip): the kept rows of W2.T / W1 are picked while the fragments are read, so W1 is used
+    // in place and no 2:4 view of the activation over all F columns is written.
     // ---- Alg. 1 -------------------------------------------------------------------------------
     // SFFN_FLAG_LEAN: the canonical copies of the packed tensors (inspection aids: w1 / w2t vals + meta, y2 vals, dy1 vals) are not
-    // written; every consumer inside the step reads the blocked copies, the 2:4 view and the compact transpose anyway
+    // written; every consumer inside the step reads the kernels' own copies
     const bool lean = (cfg->flags & SFFN_FLAG_LEAN) != 0;
+    uint16_t* vcb = a24v;                                        // the activation's survivors / metadata / regrouped offsets for eqs. (3), (7)
+    uint8_t* mcb = a24m;
+    uint8_t* cixt = a24m + up256((size_t)T * F / 16);
+    uint16_t* w2t = w2b;                                         // W2.T [F, D] per expert
+    g_dense.b_stride = F * D;
     STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
     // row pruning is per row, so the E stacked [F, D] matrices are one [E * F, D] matrix
     STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, lean ? nullptr : w1v, lean ? nullptr : w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
     {   // eq. (1), then eq. (2) + V:N:M compression on the tile while it is still in LDS
         VnmEpilogue ep;
         ep.mode = 1; ep.store_dense = keep_dense; ep.vals = lean ? nullptr : y2v; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
-        ep.v24 = a24v; ep.m24 = a24m; ep.at = atb;
+        ep.vcb = vcb; ep.mcb = mcb; ep.cixt = cixt; ep.at = atb;
         STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s, gp), "step/y1+sqrelu_vnm_compress");
     }
-    STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, lean ? nullptr : w2v, lean ? nullptr : w2m, w2vb, w2mb, w2b, s, (int)E), "step/prune24(W2.T)");
-    STAGE(launch_spmm_blocked(a24v, a24m, w2b, nullptr, T, D, F, 0, Y3, D, s, gd), "step/y3");            // eq. (3)
+    STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, lean ? nullptr : w2v, lean ? nullptr : w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
+    STAGE(launch_vnm8_gemm(vcb, mcb, cixt, w2t, D, T, D, F, Y3, D, s, gd), "step/y3");                         // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
     STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
     STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");                          // eq. (5)
-    {   // eq. (4), then eq. (6) on y2's kept slots; overwrites the 2:4 view and the transposed tile with dy1's
+    {   // eq. (4), then eq. (6) on y2's kept slots; overwrites the survivors and the transposed tile with dy1's
         VnmEpilogue ep;
-        ep.mode = 2; ep.store_dense = keep_dense; ep.vals = (lean && !gather_dx) ? nullptr : dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
-        ep.v24 = gather_dx ? nullptr : a24v; ep.m24 = a24m; ep.at = atb;
+        ep.mode = 2; ep.store_dense = keep_dense; ep.vals = lean ? nullptr : dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
+        ep.vcb = vcb; ep.at = atb;
         STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, ep, s, gp), "step/dy2+dsqrelu_vnm");
     }
-    if (gather_dx) {
-        STAGE(launch_vnm_spmm_gather(dy1v, y2m, cix, W1, D, T, D, F, 8, dX, D, s), "step/dX");                // eq. (7)
-    } else {
-        STAGE(launch_transpose(W1, F, D, D, w1tb, 1, nullptr, s, (int)E), "step/W1.T");
-        STAGE(launch_spmm_blocked(a24v, a24m, w1tb, nullptr, T, D, F, 0, dX, D, s, gd), "step/dX");       // eq. (7)
-    }
+    STAGE(launch_vnm8_gemm(vcb, mcb, cixt, W1, D, T, D, F, dX, D, s, gd), "step/dX");                          // eq. (7), dense W1 as is
     STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                           // eq. (8)
+    (void)w1tb;
     return SFFN_OK;
 }
 

@@ -109,6 +109,20 @@ __host__ __device__ __forceinline__ int64_t m8blk_off(int64_t r, int64_t k, int6
     return (((r >> 5) * KS + (k >> 7)) << 9) + ((r & 31) << 4) + ((k & 127) >> 3);
 }
 
+// Operands of the V:2:8 activation GEMM (gemm_vnm8.hip), written by the fused epilogues of eqs. (1), (4):
+// survivors (element index of the pair of (token t, column block blk); F = d_ffn): 1 KB per (32 tokens, 64 hidden units)
+__host__ __device__ __forceinline__ int64_t vcb_off(int64_t t, int64_t blk, int64_t F) {
+    return ((((t >> 5) * (F >> 6) + (blk >> 3)) << 9) + ((t & 31) << 4) + ((blk & 7) << 1));
+}
+// metadata (byte address of the 4 bytes = 8 nibbles of (token t, 64 hidden units starting at column block blk8 * 8))
+__host__ __device__ __forceinline__ int64_t mcb_off(int64_t t, int64_t blk8, int64_t F) {
+    return (((t >> 6) * (F >> 6) + blk8) << 8) + ((t & 63) << 2);
+}
+// kept-column offsets, regrouped per (64 hidden units, token block) into the 8 words the transposing reads want (byte address of word 0)
+__host__ __device__ __forceinline__ int64_t cixt_off(int64_t tb, int64_t blk8, int64_t n_tok_blocks) {
+    return (blk8 * n_tok_blocks + tb) << 5;
+}
+
 // Two survivors per 8 columns leave at most two per aligned group of four, so a V:2:8 row block is
 // also two plain 2:4 groups.  Inputs: v = the two survivors (low half first), nib = their positions
 // among the four kept columns, cw = the four kept column offsets (one per byte).  Outputs: the two

@@ -616,6 +616,14 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         ep.kmask[(int64_t)(t0 >> 6) * nblk + (f0 >> 3) + (lane >> 3)] = (uint8_t)bits;
                     }
                     cw = (uint32_t)__shfl((int)mine, bl * 8, 64);
+                    if (!FP8 && ep.cixt) {      // the same offsets regrouped for the transposing reads of gemm_vnm8.hip: word q = (h, r), byte j
+                        const int q = lane & 7, hq = q >> 2, rq = q & 3;
+                        uint32_t dw = 0;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            dw |= (((uint32_t)__shfl((int)mine, (4 * (j >> 1) + (j & 1) + 2 * hq) * 8, 64) >> (8 * rq)) & 0xFFu) << (8 * j);
+                        if (valid && lane < 8) *reinterpret_cast<uint32_t*>(ep.cixt + cixt_off(t0 >> 6, f0 >> 6, tok_ld >> 6) + q * 4) = dw;
+                    }
                 } else {
                     cw = valid ? *reinterpret_cast<const uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblk + blk_g) * 4) : 0x03020100u;
                 }
@@ -626,6 +634,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                 // fp8: v24 holds pairs of codes (4 codes per block = 2 pairs), m24 is in the fp8 metadata units
                 uint16_t* v24_p = FP8 ? ep.v24 + blk_off(t0 + (lane >> 3), blk_g * 2, F / 128) : ep.v24 + blk_off(t0 + (lane >> 3), blk_g * 4, F / 64);
                 uint8_t* m24_p = FP8 ? ep.m24 : ep.m24 + mblk_off(t0 + (lane >> 3), blk_g * 8, F / 64);      // (fp8: address per sweep, below)
+                uint32_t* vcb_p = FP8 ? nullptr : reinterpret_cast<uint32_t*>(ep.vcb + vcb_off(t0 + (lane >> 3), blk_g, F));    // sweep it: + (it / 4) 32-token groups + 8 (it % 4) tokens
+                uint8_t* mcb_p = FP8 ? nullptr : ep.mcb + mcb_off(t0 + (lane >> 3), f0 >> 6, F);                                // + 8 tokens per sweep = + 32 bytes
                 const uint32_t c0 = (cw & 0xFFu) * 2, c1 = ((cw >> 8) & 0xFFu) * 2, c2 = ((cw >> 16) & 0xFFu) * 2, c3 = (cw >> 24) * 2;
                 uint32_t pre_m[8], pre_y[8];                                // EPI 2: saved metadata and y1 of the 8 sweeps, fetched together
                 if (EPI == 2 && valid) {
@@ -662,6 +672,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             mw |= row_shl<2>(mw) << 8;
                             mw |= row_shl<4>(mw) << 16;
                             if (bl == 0) *reinterpret_cast<uint32_t*>(meta_p + (int64_t)it * 8 * (F / 16)) = mw;
+                            if (!FP8 && ep.mcb && bl == 0) *reinterpret_cast<uint32_t*>(mcb_p + it * 32) = mw;
                         } else {
                             const uint32_t mb = pre_m[it];
                             const uint32_t yk = pre_y[it];
@@ -675,6 +686,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             if (ep.vals) vals_p[(int64_t)it * 8 * (F / 8)] = v;
                         }
                         if (FP8) vmax = __builtin_fmaxf(vmax, __builtin_fmaxf(__builtin_fabsf(bf2f(v & 0xFFFFu)), __builtin_fabsf(bf2f(v >> 16))));
+                        if (!FP8 && ep.vcb) vcb_p[(int64_t)(it >> 2) * (F >> 6) * 256 + (it & 3) * 64] = v;     // operand of eq. (3) / eq. (7) on the V:2:8 kernel
                         // the same block as two plain 2:4 groups (blocked operand of eq. (3) / eq. (7))
                         if (ep.v24) {       // (not wanted when eq. (7) gathers rows from the canonical arrays)
                             uint32_t a24, b24, mb8;

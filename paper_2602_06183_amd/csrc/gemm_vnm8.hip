@@ -1,0 +1,276 @@
+// Eqs. (3), (7) of the paper for V:2:8 activations (V = 64, M = 8: the fused step's own format) without re-expressing the activation as a
+// plain 2:4 matrix over all F columns:
+//     out[t, n] = sum_k' Ac[t, k'] * Wk[row(t / 64, k'), n],      row(tb, k') = (k' / 4) * 8 + colidx[tb, k' / 4, k' % 4]
+// Ac = the packed activation read as a 2:4 matrix of logical width K' = F / 2 (two survivors per four kept columns), Wk = [F, ldw]
+// with the contraction index as row (W2.T for eq. (3), W1 as it is for eq. (7)).  The plain-2:4 route of gemm_v2.hip issues one
+// structured-sparse matrix instruction per 32 columns of F; this kernel issues one per 64, and fetches half the activation bytes.
+//
+// Tile: 256 tokens x 256 output columns, 8 wavefronts as 2 (token halves) x 4 (column quarters), as in gemm_v2.hip.  A 64-row tile (the
+// gathered-row kernel of gemm_gather.hip, which fetches only the kept rows) halves the reuse of Wk and is bound by L2 -> LDS delivery at
+// M = 8; here the whole [64 f x 256 n] slab of Wk of a stage goes to LDS once for the tile's four token blocks, and each token block picks
+// its kept rows when it READS its B fragments: ds_read_b64_tr_b16 takes one address per lane (inside a group of 16 lanes, lane s supplies 4
+// consecutive elements of row s / 4, lane l receives element l of those 4 rows), so the 4 rows of a read are the 4 kept hidden units of
+// one column block.  The 64-byte pieces of a slab row are XOR-swizzled by f % 8: the four rows of a read lie in one group of 8 rows and
+// therefore in four different pieces.
+//
+// Operands as the fused epilogues of eqs. (1), (4) write them (common.hpp: vcb_off, mcb_off, cixt_off):
+//   values    [T / 32][F / 64][32 tokens][16 values]   1 KB per (32 tokens, 64 hidden units): one wave-wide LDS-DMA load
+//   metadata  [T / 64][F / 64][64 tokens][4 bytes]     the canonical nibbles of the 8 column blocks of a stage
+//   offsets   [F / 64][T / 64][8 words]                word (h, r), byte j = kept column r of column block 4 (j / 2) + j % 2 + 2 h of the
+//                                                      stage: the four rows that lane (h = lane / 32, r = (lane % 16) / 4) addresses in read j
+// A stage = 64 hidden units = 32 k' = one matrix instruction step per fragment pair; 3 stages of 41.25 KB.
+#include "common.hpp"
+#include "kernels.hpp"
+#include "lds_dma.hpp"
+
+namespace sffn {
+
+namespace {
+
+constexpr int kStages = 3;
+constexpr int kB = 64 * 512, kA = 256 * 32, kMt = 256 * 4, kC = 256;
+constexpr int kStage = kB + kA + kMt + kC;           // 42240 bytes
+constexpr int kLoads = 4 + 1 + 1 + 1;                // per wave per stage
+// Measurement switches (wrong results by design): SFFN_VNM8_NO_MFMA leaves the matrix instructions out, SFFN_VNM8_NO_DMA the loads after the
+// prologue, SFFN_VNM8_NO_BREAD the transposing reads of the B fragments.
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+}  // namespace
+
+__global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restrict__ vcb, const uint8_t* __restrict__ mcb,
+                                                       const uint8_t* __restrict__ cixt, const uint16_t* __restrict__ Wk, int ldw,
+                                                       int Ra, int N, int F, int Ttot, uint16_t* __restrict__ out, int64_t ldo,
+                                                       int tiles_m, int tiles_n, GemmGroup grp) {
+    constexpr int WM = 128, WN = 64;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[kStages * kStage];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    int L;
+    {
+        const int n = gridDim.x, pid = blockIdx.x, per = n >> 3;
+        L = (pid < per * 8) ? (pid & 7) * per + (pid >> 3) : pid;
+    }
+    // Grouped form (role 0): the token tiles of segment e meet expert e's matrix
+    int i_base = 0;
+    if (grp.n) {
+        int e = 0, cnt = 0;
+        for (; e < grp.n; ++e) {
+            cnt = ((grp.seg[e + 1] - grp.seg[e] + 255) >> 8) * tiles_n;
+            if (L < cnt) break;
+            L -= cnt;
+        }
+        if (e == grp.n) return;
+        tiles_m = cnt / tiles_n; i_base = grp.seg[e]; Ra = grp.seg[e + 1];
+        Wk += e * grp.b_stride;
+    }
+    int tm, tn;
+    {
+        constexpr int GROUP = SFFN_TILE_GROUP;
+        const int width = GROUP * tiles_n, group = L / width, first = group * GROUP;
+        const int gsz = (tiles_m - first) < GROUP ? (tiles_m - first) : GROUP;
+        tm = first + (L % width) % gsz;
+        tn = (L % width) / gsz;
+    }
+    const int i0 = i_base + tm * 256, n0 = tn * 256;
+    const int KS = F >> 6;                               // stages = 64-wide slabs of hidden units
+    const int NTB = Ttot >> 6;
+
+    // ---- DMA sources (wave-uniform 64-bit base + 32-bit per-lane offset).  Token groups past the end of the operand are clamped into it:
+    //      they only feed outputs that are never stored. ----------------------------------------------------------------------------------
+    // B: load i of wave w (i = 0..3) brings slab rows 2 (4 w + i) + lane / 32; lane % 32 is the 16-byte slot inside the 512-byte row and
+    // fetches the chunk whose 64-byte piece the swizzle puts there.  Chunks past the right edge of Wk are redirected into the first 64 columns.
+    const uint64_t w_base = uniform64(Wk);
+    uint32_t b_lane[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = 2 * (4 * wave + i) + lh, slot = l32;
+        int c = (((slot >> 2) ^ (row & 7)) << 2) | (slot & 3);
+        if (n0 + c * 8 >= N) c &= 7;
+        b_lane[i] = (uint32_t)row * (uint32_t)ldw * 2u + (uint32_t)(n0 + c * 8) * 2u;
+    }
+    const uint32_t b_kstep = 64u * (uint32_t)ldw * 2u;
+    uint64_t a_base, m_base, c_base;
+    uint32_t a_lane, m_lane, c_lane;
+    {
+        int g32 = (i0 >> 5) + wave;                      // the wave's 32 tokens of the tile
+        g32 = g32 < (Ttot >> 5) ? g32 : (Ttot >> 5) - 1;
+        a_base = uniform64(vcb + (int64_t)g32 * KS * 512);
+        const int row = lane >> 1, slot = lane & 1;
+        a_lane = (uint32_t)(row * 32 + ((slot ^ ((row >> 3) & 1)) << 4));
+        int g64 = (i0 >> 6) + (wave & 3);                // waves w and w + 4 fetch the same 64 tokens' metadata
+        g64 = g64 < NTB ? g64 : NTB - 1;
+        m_base = uniform64(mcb + (int64_t)g64 * KS * 256);
+        m_lane = lane * 4;
+        // offsets of the tile's four token blocks: 4 x 32 bytes, every wave fetches all of them (lanes 32-63 repeat lanes 0-31)
+        int tb = (i0 >> 6) + (l32 >> 3);
+        tb = tb < NTB ? tb : NTB - 1;
+        c_base = uniform64(cixt);
+        c_lane = (uint32_t)(tb * 32 + (lane & 7) * 4);
+    }
+    const uint32_t c_kstep = (uint32_t)NTB * 32u;
+    auto issue_half = [&](int kt, int stage, int h) {
+#ifdef SFFN_VNM8_NO_DMA
+        if (kt >= kStages) return;
+#endif
+        unsigned char* sb = smem + stage * kStage;
+        unsigned char* sa = sb + kB;
+        unsigned char* sm = sa + kA;
+        unsigned char* sc = sm + kMt;
+        if (h == 0) {
+            dma16(w_base, b_lane[0] + (uint32_t)kt * b_kstep, sb + (4 * wave + 0) * 1024);
+            dma16(w_base, b_lane[1] + (uint32_t)kt * b_kstep, sb + (4 * wave + 1) * 1024);
+            dma16(a_base, a_lane + (uint32_t)kt * 1024u, sa + wave * 1024);
+            dma4(c_base, c_lane + (uint32_t)kt * c_kstep, sc);
+        } else {
+            dma16(w_base, b_lane[2] + (uint32_t)kt * b_kstep, sb + (4 * wave + 2) * 1024);
+            dma16(w_base, b_lane[3] + (uint32_t)kt * b_kstep, sb + (4 * wave + 3) * 1024);
+            dma4(m_base, m_lane + (uint32_t)kt * 256u, sm + (wave & 3) * 256);
+        }
+    };
+    auto issue = [&](int kt, int stage) { issue_half(kt, stage, 0); issue_half(kt, stage, 1); };
+
+    // ---- per-lane LDS offsets of the fragment reads (inside a stage) ---------------------------------------------------------------------
+    int a_off[4], m_off[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int row = wm * WM + a * 32 + l32;
+        a_off[a] = kB + row * 32 + ((lh ^ ((row >> 3) & 1)) << 4);
+        m_off[a] = kB + kA + row * 4 + 2 * lh;
+    }
+    // transpose read j of fragment fn: slab row = 8 cb(j) + c with cb(j) = 4 (j / 2) + j % 2 + 2 h and c = byte j of the lane's offsets word;
+    // byte address = row * 512 + ((2 wn + fn) ^ c) * 64 + 32 (column half) + 8 (lane % 4)
+    const int r4 = (lane & 15) >> 2, g = lane >> 4;
+    const int c_off = kB + kA + kMt + (lh * 4 + r4) * 4;             // + 32 * (token block of the tile)
+    const int b_fix = ((g & 1) << 5) + ((lane & 3) << 3);
+    int b_cb[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) b_cb[j] = (4 * (j >> 1) + (j & 1) + 2 * lh) * 8 * 512 + b_fix;
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
+
+    // One fragment set per token block of the wave's 128 tokens: two A fragments (32 tokens each) and the two B fragments gathered for it
+    struct FragSet {
+        Frag8 a[2];
+        int idx[2];
+        union { s16x4 q[4]; bf16x16 v; } b[2];
+    };
+    auto read_set = [&](FragSet& f, const unsigned char* st, int tbi) {
+        const uint32_t cw = *reinterpret_cast<const uint32_t*>(st + c_off + 32 * (2 * wm + tbi));
+#pragma unroll
+        for (int a2 = 0; a2 < 2; ++a2) {
+            f.a[a2].u = *reinterpret_cast<const uint4*>(st + a_off[2 * tbi + a2]);
+            f.idx[a2] = *reinterpret_cast<const uint16_t*>(st + m_off[2 * tbi + a2]);
+        }
+#ifdef SFFN_VNM8_NO_BREAD
+        f.b[0].q[0][0] = (short)cw; f.b[1].q[0][0] = (short)(cw >> 16);
+        return;
+#endif
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t c = (cw >> (8 * j)) & 7u;
+            const uint32_t addr = (uint32_t)b_cb[j] + c * 512u + (((2u * wn) ^ c) << 6);
+            f.b[0].q[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(st + addr));
+            f.b[1].q[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(st + (addr ^ 64u)));
+        }
+    };
+    auto mma_set = [&](const FragSet& f, int tbi) {
+#ifdef SFFN_VNM8_NO_MFMA
+        acc[2 * tbi][0][0] += __builtin_bit_cast(float, f.a[0].u.x) + __builtin_bit_cast(float, f.a[1].u.x) + (float)f.b[0].q[0][0] + (float)f.b[1].q[3][3] + (float)f.idx[0] + (float)f.idx[1];
+        return;
+#endif
+#pragma unroll
+        for (int a2 = 0; a2 < 2; ++a2)
+#pragma unroll
+            for (int fn = 0; fn < 2; ++fn)
+                acc[2 * tbi + a2][fn] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[a2].v, f.b[fn].v, acc[2 * tbi + a2][fn], f.idx[a2], 0, 0);
+    };
+#define SB() __builtin_amdgcn_sched_barrier(0)
+
+    const int nk = KS;
+#pragma unroll
+    for (int p = 0; p < kStages; ++p) issue(p < nk ? p : nk - 1, p);
+    wait_vmcnt<(kStages - 1) * kLoads>();
+    __syncthreads();
+    FragSet P, Q;
+    read_set(P, smem, 0);
+    int stage = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+        const int nxt = (kt + kStages < nk) ? kt + kStages : nk - 1;
+        const int next_stage = (stage + 1 == kStages) ? 0 : stage + 1;
+        const unsigned char* st = smem + stage * kStage;
+        const unsigned char* sn = smem + next_stage * kStage;
+        mma_set(P, 0); SB();
+        read_set(Q, st, 1); SB();
+        // Q has arrived and this wave's part of tile kt + 1 has landed; after the barrier every wave is done reading this stage, which is
+        // refilled at once
+        wait_vmcnt_lgkm0<(kStages - 2) * kLoads>();
+        __builtin_amdgcn_s_barrier();
+        SB();
+        issue_half(nxt, stage, 0); SB();
+        mma_set(Q, 1); SB();
+        issue_half(nxt, stage, 1); SB();
+        read_set(P, sn, 0); SB();
+        stage = next_stage;
+    }
+#undef SB
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    // ---- output: every wave's 32 x 64 sub-tiles go through LDS as [t][n] so that HBM sees 128-byte row segments ----------------------------
+    constexpr int EP = WN * 2 + 16;
+    unsigned char* scratch = smem + wave * (32 * EP);
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = 8 * (r >> 2) + 4 * lh + (r & 3);
+                *reinterpret_cast<uint16_t*>(scratch + row * EP + (b * 32 + l32) * 2) = (uint16_t)f2bf(acc[a][b][r]);
+            }
+        wave_lds_sync();
+        constexpr int CH = WN / 8;
+#pragma unroll
+        for (int p = 0; p < 32 * CH / 64; ++p) {
+            const int e = lane + 64 * p, row = e / CH, ch = e % CH;
+            const int i = i0 + wm * WM + a * 32 + row, j = n0 + wn * WN + ch * 8;
+            if (i < Ra && j < N) *reinterpret_cast<uint4*>(out + (int64_t)i * ldo + j) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
+        }
+        wave_lds_sync();
+    }
+}
+
+bool vnm8_gemm_ok(int64_t T, int64_t N, int64_t F, int64_t ldw) {
+    return T > 0 && T % 64 == 0 && N > 0 && N % 64 == 0 && F > 0 && F % 64 == 0 && ldw >= N && ldw % 8 == 0 && F * ldw * 2 < ((int64_t)1 << 32);
+}
+
+hipError_t launch_vnm8_gemm(const uint16_t* vcb, const uint8_t* mcb, const uint8_t* cixt, const uint16_t* Wk, int64_t ldw, int64_t T, int64_t N,
+                            int64_t F, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp) {
+    if (!vnm8_gemm_ok(T, N, F, ldw)) return hipErrorInvalidValue;
+    const GemmGroup g = grp ? *grp : GemmGroup();
+    if (g.n && (g.role != 0 || g.seg_dev || g.n > GemmGroup::kMaxExperts)) return hipErrorInvalidValue;
+    const int tiles_m = (int)((T + 255) / 256), tiles_n = (int)((N + 255) / 256);
+    int tiles = tiles_m * tiles_n;
+    if (g.n) {
+        tiles = 0;
+        for (int e = 0; e < g.n; ++e) tiles += (g.seg[e + 1] - g.seg[e] + 255) / 256 * tiles_n;
+    }
+    if (tiles == 0) return hipSuccess;
+    hipLaunchKernelGGL(vnm8_gemm_kernel, dim3((unsigned)tiles), dim3(512), 0, s, vcb, mcb, cixt, Wk, (int)ldw, (int)T, (int)N, (int)F, (int)T, out, ldo,
+                       tiles_m, tiles_n, g);
+    return hipGetLastError();
+}
+
+}  // namespace sffn

@@ -42,6 +42,11 @@ struct VnmEpilogue {
     float inv_out = 1.0f;
     int at_fp8 = 0;                 // fp8 modes 1 / 2: `at` receives codes (pairs in the blocked layout, [F / 2, T]) instead of bf16
     float* amax = nullptr;          // fp8 modes 1 / 2: amax slots for the survivors' magnitudes (y2 / dy1)
+    // modes 1 / 2, bf16: the operands of the V:2:8 activation GEMM (gemm_vnm8.hip; layouts: vcb_off, mcb_off, cixt_off in common.hpp):
+    // vcb = the survivors (both modes), mcb = their metadata and cixt = the regrouped kept-column offsets (mode 1; mode 2 reuses them)
+    uint16_t* vcb = nullptr;
+    uint8_t* mcb = nullptr;
+    uint8_t* cixt = nullptr;
 };
 
 // Grouped (mixture-of-experts) form of a contraction: the token axis is cut into n consecutive segments, one per
@@ -96,6 +101,11 @@ bool vnm_spmm_gather_ok(int64_t T, int64_t N, int64_t F, int M);
 // grp (role 0, host segment table): the token blocks of segment e take expert e's matrix Wk + e * b_stride.
 hipError_t launch_vnm_spmm_gather(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* colidx, const uint16_t* Wk, int64_t ldw,
                                   int64_t T, int64_t N, int64_t F, int M, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
+// eqs. (3), (7) for M = 8 on a 256-token tile (gemm_vnm8.hip): the activation as the epilogues' vcb / mcb / cixt arrays, Wk = [F, ldw] with the
+// contraction index as row; T, N, F multiples of 64.  grp as above (b_stride in elements).
+bool vnm8_gemm_ok(int64_t T, int64_t N, int64_t F, int64_t ldw);
+hipError_t launch_vnm8_gemm(const uint16_t* vcb, const uint8_t* mcb, const uint8_t* cixt, const uint16_t* Wk, int64_t ldw, int64_t T, int64_t N,
+                            int64_t F, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 // The same on E4M3 codes: a_codes [T, 2 F / M] + the same metadata and column offsets, Wq = codes [F, ldw bytes], out = bf16(alpha * sum);
 // 4 F / M a multiple of 128; b_stride of grp in bytes.
 bool vnm_spmm_gather_fp8_ok(int64_t T, int64_t N, int64_t F, int M);
