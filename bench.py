@@ -25,6 +25,7 @@ HBM_PEAK_GBS = 8000.0
 SPARSE_GEMM = "gemm_nt_v2_kernel<sparse A, smfmac_f32_32x32x32_bf16>"
 DENSE_GEMM = "gemm_nt_v2_kernel<dense A, mfma_f32_32x32x16_bf16>"
 WGRAD = "wgrad_vnm_kernel<compact V:N:M A, mfma_f32_32x32x16_bf16>"
+VNM8_GEMM = "vnm8_gemm_kernel<V:2:8 A, smfmac_f32_32x32x32_bf16>"
 ROUTER_GEMMS = ("router/y1c+sqrelu+2:4", "router/dy2c+dsqrelu", "router/y3", "router/dX", "router/dW2.T", "router/dW1")
 
 
@@ -38,13 +39,14 @@ def algorithmic_flops(stage, T, D, F, M=8):
             "step/y3": act, "step/dX": act, "step/dW2": act, "step/dW1": act}.get(stage)
 
 
-def executed_flops(stage, T, D, F, M=8):
+def executed_flops(stage, T, D, F, M=8, gathered=True):
     """Flops the matrix cores are issued for (dense-equivalent of the instructions used)."""
     tdf = float(T) * D * F
     if stage.startswith("router/"):
         return 8.0 / M * tdf if stage in ROUTER_GEMMS else None
+    act = (8.0 / M * tdf) if gathered else 2 * tdf              # eqs. (3), (7): only the kept columns are contracted / all F as plain 2:4
     return {"step/y1+sqrelu_vnm_compress": 2 * tdf, "step/dy2+dsqrelu_vnm": 2 * tdf, "step/y1": 2 * tdf, "step/dy2": 2 * tdf,
-            "step/y3": 2 * tdf, "step/dX": 2 * tdf, "step/dW2": 2 * tdf, "step/dW1": 2 * tdf}.get(stage)
+            "step/y3": act, "step/dX": act, "step/dW2": 2 * tdf, "step/dW1": 2 * tdf}.get(stage)
 
 
 KERNEL_OF_STAGE = {"step/y1+sqrelu_vnm_compress": SPARSE_GEMM, "step/dy2+dsqrelu_vnm": SPARSE_GEMM, "step/y1": SPARSE_GEMM, "step/dy2": SPARSE_GEMM,
@@ -305,8 +307,8 @@ def main():
     sffn.profile_enable(False)
     by_kernel = {}
     kos = dict(KERNEL_OF_STAGE)
-    if "step/dX" in acc and "step/W1.T" not in acc and M == 8:      # eq. (7) ran on the gathered-row kernel (no transpose of W1 in the step)
-        kos["step/dX"] = "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>"
+    if M == 8 and not args.router:      # eqs. (3), (7) contract the V:2:8 activation as it is, kept rows picked at the fragment reads
+        kos.update({"step/y3": VNM8_GEMM, "step/dX": VNM8_GEMM})
     if M != 8:      # wide blocks: eqs. (3), (7) gather rows, eqs. (5), (8) contract the dense transposed activation with the dense-operand tile kernel
         if "step/to24(y2)" not in acc:
             kos.update({"step/y3": "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>", "step/dX": "vnm_spmm_gather_kernel<smfmac_f32_32x32x32_bf16>"})
@@ -318,7 +320,8 @@ def main():
     launches = by_kernel[dom_kernel]
     avg_ms = sum(ms for _, ms in launches) / len(launches)
     alg = sum(algorithmic_flops(n, T, D, F, M) or 0.0 for n, _ in launches) / len(launches)
-    exe = sum(executed_flops(n, T, D, F, M) or 0.0 for n, _ in launches) / len(launches)
+    gathered = "step/to24(y2)" not in acc
+    exe = sum(executed_flops(n, T, D, F, M, gathered) or 0.0 for n, _ in launches) / len(launches)
     achieved = alg / (avg_ms * 1e-3) / 1e12
     # HBM bytes per launch of that kernel: from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes of this same command, scaled by a
     # plain copy (the summaries and the scale factors are in profiles/; counters cannot be read from inside the timed process)
@@ -331,6 +334,18 @@ def main():
                 "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
                 "issued": round(exe / (avg_ms * 1e-3) / 1e12, 2), "issued_frac": round(exe / (avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    # the same figures for every contraction kernel of the step (the object above is the one with the largest share of the step)
+    per_kernel = []
+    for kname, ls in sorted(by_kernel.items(), key=lambda kv: -sum(ms for _, ms in kv[1])):
+        a = sum(algorithmic_flops(n, T, D, F, M) or 0.0 for n, _ in ls) / len(ls)
+        if a <= 0:
+            continue
+        e = sum(executed_flops(n, T, D, F, M, gathered) or 0.0 for n, _ in ls) / len(ls)
+        ms = sum(v for _, v in ls) / len(ls)
+        per_kernel.append({"kernel": kname, "launches": [n for n, _ in ls], "avg_launch_ms": round(ms, 4), "step_share": round(sum(v for _, v in ls) / sum(acc.values()), 3),
+                           "achieved": round(a / (ms * 1e-3) / 1e12, 2), "frac": round(a / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                           "issued_frac": round(e / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)})
+    roofline["kernels"] = per_kernel
     head = hw.summary(res)
 
     # ---- CPU oracle on the host cores: a bounded sample of the same workload -------------------------------------

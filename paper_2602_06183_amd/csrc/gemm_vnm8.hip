@@ -5,7 +5,7 @@
 // with the contraction index as row (W2.T for eq. (3), W1 as it is for eq. (7)).  The plain-2:4 route of gemm_v2.hip issues one
 // structured-sparse matrix instruction per 32 columns of F; this kernel issues one per 64, and fetches half the activation bytes.
 //
-// Tile: 256 tokens x 256 output columns, 8 wavefronts as 2 (token halves) x 4 (column quarters), as in gemm_v2.hip.  A 64-row tile (the
+// Tile: 256 tokens x 256 output columns, 8 wavefronts as 4 (token blocks) x 2 (column halves).  A 64-row tile (the
 // gathered-row kernel of gemm_gather.hip, which fetches only the kept rows) halves the reuse of Wk and is bound by L2 -> LDS delivery at
 // M = 8; here the whole [64 f x 256 n] slab of Wk of a stage goes to LDS once for the tile's four token blocks, and each token block picks
 // its kept rows when it READS its B fragments: ds_read_b64_tr_b16 takes one address per lane (inside a group of 16 lanes, lane s supplies 4
@@ -43,12 +43,10 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
                                                        const uint8_t* __restrict__ cixt, const uint16_t* __restrict__ Wk, int ldw,
                                                        int Ra, int N, int F, int Ttot, uint16_t* __restrict__ out, int64_t ldo,
                                                        int tiles_m, int tiles_n, GemmGroup grp) {
-    constexpr int WM = 128, WN = 64;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kStages * kStage];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 2, wn = wave & 3;
     const int l32 = lane & 31, lh = lane >> 5;
 
     int L;
@@ -135,44 +133,46 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
     };
     auto issue = [&](int kt, int stage) { issue_half(kt, stage, 0); issue_half(kt, stage, 1); };
 
-    // ---- per-lane LDS offsets of the fragment reads (inside a stage) ---------------------------------------------------------------------
-    int a_off[4], m_off[4];
+    // ---- per-lane LDS offsets of the fragment reads (inside a stage).  A wave owns one token block (64 tokens) x 128 output columns: its two
+    //      A fragments are read by one other wave only, and the four B fragments it gathers belong to one column selection. ----------------------
+    const int tbw = wave >> 1, nh = wave & 1;
+    int a_off[2], m_off[2];
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        const int row = wm * WM + a * 32 + l32;
+    for (int a = 0; a < 2; ++a) {
+        const int row = tbw * 64 + a * 32 + l32;
         a_off[a] = kB + row * 32 + ((lh ^ ((row >> 3) & 1)) << 4);
         m_off[a] = kB + kA + row * 4 + 2 * lh;
     }
     // transpose read j of fragment fn: slab row = 8 cb(j) + c with cb(j) = 4 (j / 2) + j % 2 + 2 h and c = byte j of the lane's offsets word;
-    // byte address = row * 512 + ((2 wn + fn) ^ c) * 64 + 32 (column half) + 8 (lane % 4)
+    // byte address = row * 512 + ((4 nh + fn) ^ c) * 64 + 32 (column half) + 8 (lane % 4)
     const int r4 = (lane & 15) >> 2, g = lane >> 4;
-    const int c_off = kB + kA + kMt + (lh * 4 + r4) * 4;             // + 32 * (token block of the tile)
+    const int c_off = kB + kA + kMt + 32 * tbw + (lh * 4 + r4) * 4;
     const int b_fix = ((g & 1) << 5) + ((lane & 3) << 3);
     int b_cb[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) b_cb[j] = (4 * (j >> 1) + (j & 1) + 2 * lh) * 8 * 512 + b_fix;
 
-    f32x16 acc[4][2];
+    f32x16 acc[2][4];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
 
-    // One fragment set per token block of the wave's 128 tokens: two A fragments (32 tokens each) and the two B fragments gathered for it
-    struct FragSet {
-        Frag8 a[2];
-        int idx[2];
-        union { s16x4 q[4]; bf16x16 v; } b[2];
-    };
-    auto read_set = [&](FragSet& f, const unsigned char* st, int tbi) {
-        const uint32_t cw = *reinterpret_cast<const uint32_t*>(st + c_off + 32 * (2 * wm + tbi));
+    // The stage's fragments in two halves: P = both A fragments, the offsets word and B fragments 0, 1; Q = B fragments 2, 3 (the A
+    // fragments of P stay live until Q's matrix instructions, so A is double-buffered by stage parity)
+    struct BPair { union { s16x4 q[4]; bf16x16 v; } b[2]; };
+    struct AFrags { Frag8 a[2]; int idx[2]; uint32_t cw; };
+    auto read_a = [&](AFrags& f, const unsigned char* st) {
+        f.cw = *reinterpret_cast<const uint32_t*>(st + c_off);
 #pragma unroll
         for (int a2 = 0; a2 < 2; ++a2) {
-            f.a[a2].u = *reinterpret_cast<const uint4*>(st + a_off[2 * tbi + a2]);
-            f.idx[a2] = *reinterpret_cast<const uint16_t*>(st + m_off[2 * tbi + a2]);
+            f.a[a2].u = *reinterpret_cast<const uint4*>(st + a_off[a2]);
+            f.idx[a2] = *reinterpret_cast<const uint16_t*>(st + m_off[a2]);
         }
+    };
+    auto read_b = [&](BPair& f, const unsigned char* st, uint32_t cw, int half) {
 #ifdef SFFN_VNM8_NO_BREAD
         f.b[0].q[0][0] = (short)cw; f.b[1].q[0][0] = (short)(cw >> 16);
         return;
@@ -180,21 +180,21 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t c = (cw >> (8 * j)) & 7u;
-            const uint32_t addr = (uint32_t)b_cb[j] + c * 512u + (((2u * wn) ^ c) << 6);
+            const uint32_t addr = (uint32_t)b_cb[j] + c * 512u + (((4u * nh + 2u * half) ^ c) << 6);
             f.b[0].q[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(st + addr));
             f.b[1].q[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(st + (addr ^ 64u)));
         }
     };
-    auto mma_set = [&](const FragSet& f, int tbi) {
+    auto mma_half = [&](const AFrags& fa, const BPair& fb, int half) {
 #ifdef SFFN_VNM8_NO_MFMA
-        acc[2 * tbi][0][0] += __builtin_bit_cast(float, f.a[0].u.x) + __builtin_bit_cast(float, f.a[1].u.x) + (float)f.b[0].q[0][0] + (float)f.b[1].q[3][3] + (float)f.idx[0] + (float)f.idx[1];
+        acc[0][2 * half][0] += __builtin_bit_cast(float, fa.a[0].u.x) + __builtin_bit_cast(float, fa.a[1].u.x) + (float)fb.b[0].q[0][0] + (float)fb.b[1].q[3][3] + (float)fa.idx[0] + (float)fa.idx[1];
         return;
 #endif
 #pragma unroll
         for (int a2 = 0; a2 < 2; ++a2)
 #pragma unroll
             for (int fn = 0; fn < 2; ++fn)
-                acc[2 * tbi + a2][fn] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[a2].v, f.b[fn].v, acc[2 * tbi + a2][fn], f.idx[a2], 0, 0);
+                acc[a2][2 * half + fn] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(fa.a[a2].v, fb.b[fn].v, acc[a2][2 * half + fn], fa.idx[a2], 0, 0);
     };
 #define SB() __builtin_amdgcn_sched_barrier(0)
 
@@ -203,53 +203,64 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
     for (int p = 0; p < kStages; ++p) issue(p < nk ? p : nk - 1, p);
     wait_vmcnt<(kStages - 1) * kLoads>();
     __syncthreads();
-    FragSet P, Q;
-    read_set(P, smem, 0);
+    AFrags A0, A1;
+    BPair P, Q;
+    read_a(A0, smem);
+    read_b(P, smem, A0.cw, 0);
     int stage = 0;
-    for (int kt = 0; kt < nk; ++kt) {
+    // two stages per trip so that the A fragment buffers alternate without copies
+    auto step = [&](int kt, AFrags& cur, AFrags& nxt_a) {
         const int nxt = (kt + kStages < nk) ? kt + kStages : nk - 1;
         const int next_stage = (stage + 1 == kStages) ? 0 : stage + 1;
         const unsigned char* st = smem + stage * kStage;
         const unsigned char* sn = smem + next_stage * kStage;
-        mma_set(P, 0); SB();
-        read_set(Q, st, 1); SB();
+        mma_half(cur, P, 0); SB();
+        read_b(Q, st, cur.cw, 1); SB();
         // Q has arrived and this wave's part of tile kt + 1 has landed; after the barrier every wave is done reading this stage, which is
         // refilled at once
         wait_vmcnt_lgkm0<(kStages - 2) * kLoads>();
         __builtin_amdgcn_s_barrier();
         SB();
         issue_half(nxt, stage, 0); SB();
-        mma_set(Q, 1); SB();
+        read_a(nxt_a, sn); SB();
+        mma_half(cur, Q, 1); SB();
         issue_half(nxt, stage, 1); SB();
-        read_set(P, sn, 0); SB();
+        read_b(P, sn, nxt_a.cw, 0); SB();
         stage = next_stage;
+    };
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        step(kt, A0, A1);
+        step(kt + 1, A1, A0);
     }
+    if (kt < nk) step(kt, A0, A1);
 #undef SB
     wait_vmcnt<0>();
     __syncthreads();
 
-    // ---- output: every wave's 32 x 64 sub-tiles go through LDS as [t][n] so that HBM sees 128-byte row segments ----------------------------
-    constexpr int EP = WN * 2 + 16;
+    // ---- output: the wave's 32 x 64 sub-tiles go through LDS as [t][n] so that HBM sees 128-byte row segments -----------------------------
+    constexpr int EP = 64 * 2 + 16;
     unsigned char* scratch = smem + wave * (32 * EP);
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int half = 0; half < 2; ++half) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = 8 * (r >> 2) + 4 * lh + (r & 3);
-                *reinterpret_cast<uint16_t*>(scratch + row * EP + (b * 32 + l32) * 2) = (uint16_t)f2bf(acc[a][b][r]);
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 8 * (r >> 2) + 4 * lh + (r & 3);
+                    *reinterpret_cast<uint16_t*>(scratch + row * EP + (b * 32 + l32) * 2) = (uint16_t)f2bf(acc[a][2 * half + b][r]);
+                }
+            wave_lds_sync();
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int e = lane + 64 * p, row = e >> 3, ch = e & 7;
+                const int i = i0 + tbw * 64 + a * 32 + row, j = n0 + nh * 128 + half * 64 + ch * 8;
+                if (i < Ra && j < N) *reinterpret_cast<uint4*>(out + (int64_t)i * ldo + j) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
             }
-        wave_lds_sync();
-        constexpr int CH = WN / 8;
-#pragma unroll
-        for (int p = 0; p < 32 * CH / 64; ++p) {
-            const int e = lane + 64 * p, row = e / CH, ch = e % CH;
-            const int i = i0 + wm * WM + a * 32 + row, j = n0 + wn * WN + ch * 8;
-            if (i < Ra && j < N) *reinterpret_cast<uint4*>(out + (int64_t)i * ldo + j) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
+            wave_lds_sync();
         }
-        wave_lds_sync();
-    }
 }
 
 bool vnm8_gemm_ok(int64_t T, int64_t N, int64_t F, int64_t ldw) {

@@ -79,7 +79,9 @@ __global__ void __launch_bounds__(256) prune24_cols_kernel(const uint16_t* __res
     if (src_t) {        // the unpruned transposed tile: logical rows r (64) x k (128) -> [R, K] row-major, 16 bytes per thread and pass
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int e = tid + 256 * i, tr = e & 63, ks = e >> 6;       // row r0 + tr, k segment of 8 starting at 8 ks
+            // row r0 + tr, k segment of 8 starting at 8 ks; neighbouring lanes take the two halves of a 32-byte piece of one output row
+            // (whole sectors in HBM; the LDS reads of a wavefront then fall into two bank groups x 16 words: no conflicts)
+            const int e = tid + 256 * i, tr = (e >> 1) & 63, ks = ((e >> 7) << 1) | (e & 1);
             if (k0 + 8 * ks < K) {
                 uint32_t w[4];
 #pragma unroll
