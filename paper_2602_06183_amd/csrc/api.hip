@@ -472,53 +472,17 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     float *ax = slot_of(0), *aw1 = slot_of(1), *aw2 = slot_of(2), *ay2 = slot_of(3), *ady = slot_of(4), *ady1 = slot_of(5);
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
     if (amax) STAGE(launch_amax_clear(slots, 6, s), "step/clear(amax)");
-    if (cfg->M != 8) {
-        // Blocks of M = 16, 32, 64 columns (Table 5): the same readings, with the general-M epilogues and eqs. (3), (7) on the kept rows of the
-        // quantised W2.T / W1 (row-major codes, written by the two pruning passes); the survivors are codes in both directions.
-        const int M = cfg->M, logM = M == 16 ? 4 : M == 32 ? 5 : 6;
-        uint8_t *w2tq = w2q, *w1q = w1tq, *dy1c = (uint8_t*)dy1v;       // same sizes as the M = 8 step's dense quantised weights
-        GemmGroup g_rows = g;
-        g_rows.role = 0; g_rows.b_stride = F * D;
-        const GemmGroup* gr = g.n ? &g_rows : nullptr;
-        if (w8) {
-            STAGE(launch_transpose_quantize_fp8_blocked(X, T, D, D, ix, (uint8_t*)xtb, s, ax, xq), "step/quantize(X, X.T)");
-        } else {
-            STAGE(launch_transpose(X, T, D, D, xtb, 1, nullptr, s), "step/X.T");
-            STAGE(launch_quantize_fp8_blocked(X, T, D, D, ix, xq, s, ax), "step/quantize(X)");
-        }
-        for (int64_t e = 0; e < E; ++e)
-            STAGE(launch_prune24_fp8_step(W1 + e * F * D, F, D, D, 0, cfg->mode, iw1, w1c ? w1c + e * F * D / 2 : nullptr, w1m ? w1m + e * F * D / 8 : nullptr,
-                                          w1b + e * F * D / 2, w1mb + e * F * D / 8, s, nullptr, aw1, w1q + e * F * D), "step/prune24_fp8(W1)+quantize(W1)");
-        {
-            VnmEpilogue ep;
-            ep.mode = 5; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = (uint16_t*)y2c; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
-            ep.at = atb; ep.inv_out = 1.0f / sc->y2; ep.at_fp8 = w8; ep.amax = ay2;
-            STAGE(launch_gemm_fp8_blocked(w1b, w1mb, xq, b1, sc->x * sc->w1, F, T, D, y1, F, &ep, s, gp), "step/y1+sqrelu_vnm_compress");
-        }
-        for (int64_t e = 0; e < E; ++e)
-            STAGE(launch_prune24_fp8_step(W2 + e * D * F, F, D, F, 1, cfg->mode, iw2, w2c ? w2c + e * F * D / 2 : nullptr, w2m ? w2m + e * F * D / 8 : nullptr,
-                                          w2b + e * F * D / 2, w2mb + e * F * D / 8, s, nullptr, aw2, w2tq + e * F * D), "step/prune24_fp8(W2.T)+quantize(W2.T)");
-        STAGE(launch_vnm_spmm_gather_fp8(y2c, y2m, cix, w2tq, D, sc->y2 * sc->w2, T, D, F, M, Y3, D, s, gr), "step/y3");                     // eq. (3)
-        if (w8) {
-            STAGE(launch_transpose_quantize_fp8_blocked(dY, T, D, D, idy, (uint8_t*)dytb, s, ady, dyq), "step/quantize(dY, dY.T)");
-        } else {
-            STAGE(launch_transpose(dY, T, D, D, dytb, 1, nullptr, s), "step/dY.T");
-            STAGE(launch_quantize_fp8_blocked(dY, T, D, D, idy, dyq, s, ady), "step/quantize(dY)");
-        }
-        if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)dytb, sc->y2 * sc->dy, F, D, T, 1, dW2, F, s, gw), "step/dW2");
-        else    STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");
-        {
-            VnmEpilogue ep;
-            ep.mode = 6; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = (uint16_t*)dy1c; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
-            ep.at = atb; ep.inv_out = 1.0f / sc->dy1; ep.at_fp8 = w8; ep.amax = ady1;
-            STAGE(launch_gemm_fp8_blocked(w2b, w2mb, dyq, nullptr, sc->dy * sc->w2, F, T, D, dy2, F, &ep, s, gp), "step/dy2+dsqrelu_vnm");
-        }
-        STAGE(launch_vnm_spmm_gather_fp8(dy1c, y2m, cix, w1q, D, sc->dy1 * sc->w1, T, D, F, M, dX, D, s, gr), "step/dX");                   // eq. (7)
-        if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)xtb, sc->dy1 * sc->x, F, D, T, 0, dW1, D, s, gw), "step/dW1");
-        else    STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");
-        if (amax) STAGE(launch_amax_finish(slots, 6, amax, s), "step/finish(amax)");
-        return SFFN_OK;
-    }
+    // One data flow for every block width.  M = 8: the epilogues of eqs. (1), (4) also write the survivors' codes in the units of the V:2:8
+    // activation GEMM (gemm_vnm8.hip), which picks the kept rows of the quantised W2.T / W1 while it reads its fragments.  M = 16, 32, 64
+    // (Table 5): the general-M epilogues; eqs. (3), (7) fetch only the kept rows (gemm_gather.hip) and read the canonical codes.
+    const int M = cfg->M, logM = M == 8 ? 3 : M == 16 ? 4 : M == 32 ? 5 : 6;
+    const bool wide = M != 8;
+    uint8_t *w2tq = w2q, *w1q = w1tq;                   // W2.T and W1 as row-major codes [F, D] per expert (contraction index = row)
+    uint8_t* dy1c = (uint8_t*)dy1v;                     // wide blocks: dy1's survivors leave as codes only
+    uint8_t *vcb = v24, *mcb = m24, *cixt = m24 + up256((size_t)T * F / 16);
+    GemmGroup g_rows = g;
+    g_rows.role = 0; g_rows.b_stride = F * D;
+    const GemmGroup* gr = g.n ? &g_rows : nullptr;
     // ---- Alg. 1 -------------------------------------------------------------------------------
     if (w8) {       // X.T codes for eq. (8) and X codes for eq. (1) in one pass over X
         STAGE(launch_transpose_quantize_fp8_blocked(X, T, D, D, ix, (uint8_t*)xtb, s, ax, xq), "step/quantize(X, X.T)");
@@ -526,20 +490,22 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
         STAGE(launch_transpose(X, T, D, D, xtb, 1, nullptr, s), "step/X.T");                                // bf16, for eq. (8)
         STAGE(launch_quantize_fp8_blocked(X, T, D, D, ix, xq, s, ax), "step/quantize(X)");
     }
-    // W1 in one pass per expert: pruned (canonical + blocked codes) for eq. (1), dense and transposed for eq. (7)
+    // W1 in one pass per expert: pruned (canonical + blocked codes) for eq. (1), and the un-pruned W1 as codes for eq. (7)
     for (int64_t e = 0; e < E; ++e)
-        STAGE(launch_transpose_quantize_fp8_blocked(W1 + e * F * D, F, D, D, iw1, w1tq + e * D * F, s, aw1, nullptr, cfg->mode, w1c ? w1c + e * F * D / 2 : nullptr,
-                                                    w1m ? w1m + e * F * D / 8 : nullptr, w1b + e * F * D / 2, w1mb + e * F * D / 8), "step/prune24_fp8(W1)+quantize(W1.T)");
+        STAGE(launch_prune24_fp8_step(W1 + e * F * D, F, D, D, 0, cfg->mode, iw1, w1c ? w1c + e * F * D / 2 : nullptr, w1m ? w1m + e * F * D / 8 : nullptr,
+                                      w1b + e * F * D / 2, w1mb + e * F * D / 8, s, aw1, w1q + e * F * D), "step/prune24_fp8(W1)+quantize(W1)");
     {   // eq. (1) on codes, then eq. (2) + V:N:M compression on the bf16 tile; the survivors leave as codes (and in bf16 for eq. (5))
         VnmEpilogue ep;
-        ep.mode = 1; ep.store_dense = keep_dense; ep.vals = (uint16_t*)y2c; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
-        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->y2; ep.at_fp8 = w8; ep.amax = ay2;
+        ep.mode = wide ? 5 : 1; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = (uint16_t*)y2c; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask;
+        ep.ykept = ykept; ep.at = atb; ep.inv_out = 1.0f / sc->y2; ep.at_fp8 = w8; ep.amax = ay2;
+        if (!wide) { ep.vcb = (uint16_t*)vcb; ep.mcb = mcb; ep.cixt = cixt; }
         STAGE(launch_gemm_fp8_blocked(w1b, w1mb, xq, b1, sc->x * sc->w1, F, T, D, y1, F, &ep, s, gp), "step/y1+sqrelu_vnm_compress");
     }
     for (int64_t e = 0; e < E; ++e)
-        STAGE(launch_prune24_fp8_step(W2 + e * D * F, F, D, F, 1, cfg->mode, iw2, w2c ? w2c + e * F * D / 2 : nullptr, w2m ? w2m + e * F * D / 8 : nullptr, w2b + e * F * D / 2,
-                                      w2mb + e * F * D / 8, s, w2q + e * D * F, aw2), "step/prune24_fp8(W2.T)+quantize(W2)");
-    STAGE(launch_gemm_fp8_blocked(v24, m24, w2q, nullptr, sc->y2 * sc->w2, T, D, F, Y3, D, nullptr, s, gd), "step/y3");      // eq. (3)
+        STAGE(launch_prune24_fp8_step(W2 + e * D * F, F, D, F, 1, cfg->mode, iw2, w2c ? w2c + e * F * D / 2 : nullptr, w2m ? w2m + e * F * D / 8 : nullptr,
+                                      w2b + e * F * D / 2, w2mb + e * F * D / 8, s, aw2, w2tq + e * F * D), "step/prune24_fp8(W2.T)+quantize(W2.T)");
+    if (wide) STAGE(launch_vnm_spmm_gather_fp8(y2c, y2m, cix, w2tq, D, sc->y2 * sc->w2, T, D, F, M, Y3, D, s, gr), "step/y3");      // eq. (3)
+    else      STAGE(launch_vnm8_gemm_fp8(vcb, mcb, cixt, w2tq, D, sc->y2 * sc->w2, T, D, F, Y3, D, s, gr), "step/y3");
     // ---- Alg. 2 -------------------------------------------------------------------------------
     if (w8) {
         STAGE(launch_transpose_quantize_fp8_blocked(dY, T, D, D, idy, (uint8_t*)dytb, s, ady, dyq), "step/quantize(dY, dY.T)");
@@ -549,13 +515,15 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     }
     if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)dytb, sc->y2 * sc->dy, F, D, T, 1, dW2, F, s, gw), "step/dW2");   // eq. (5) on codes
     else    STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");               // eq. (5), bf16
-    {   // eq. (4) on codes, then eq. (6) in bf16 on y2's kept slots; dy1 leaves in bf16 (canonical, eq. (8)) and as codes (eq. (7))
+    {   // eq. (4) on codes, then eq. (6) in bf16 on y2's kept slots; dy1 leaves as codes (eq. (7)) and, at M = 8, in bf16 (canonical)
         VnmEpilogue ep;
-        ep.mode = 2; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
-        ep.v24 = (uint16_t*)v24; ep.m24 = m24; ep.at = atb; ep.inv_out = 1.0f / sc->dy1; ep.at_fp8 = w8; ep.amax = ady1;
+        ep.mode = wide ? 6 : 2; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = wide ? (uint16_t*)dy1c : dy1v; ep.meta = y2m; ep.colidx = cix;
+        ep.ykept = ykept; ep.at = atb; ep.inv_out = 1.0f / sc->dy1; ep.at_fp8 = w8; ep.amax = ady1;
+        if (!wide) ep.vcb = (uint16_t*)vcb;
         STAGE(launch_gemm_fp8_blocked(w2b, w2mb, dyq, nullptr, sc->dy * sc->w2, F, T, D, dy2, F, &ep, s, gp), "step/dy2+dsqrelu_vnm");
     }
-    STAGE(launch_gemm_fp8_blocked(v24, m24, w1tq, nullptr, sc->dy1 * sc->w1, T, D, F, dX, D, nullptr, s, gd), "step/dX");      // eq. (7)
+    if (wide) STAGE(launch_vnm_spmm_gather_fp8(dy1c, y2m, cix, w1q, D, sc->dy1 * sc->w1, T, D, F, M, dX, D, s, gr), "step/dX");     // eq. (7)
+    else      STAGE(launch_vnm8_gemm_fp8(vcb, mcb, cixt, w1q, D, sc->dy1 * sc->w1, T, D, F, dX, D, s, gr), "step/dX");
     if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)xtb, sc->dy1 * sc->x, F, D, T, 0, dW1, D, s, gw), "step/dW1");   // eq. (8) on codes
     else    STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                // eq. (8), bf16
     if (amax) STAGE(launch_amax_finish(slots, 6, amax, s), "step/finish(amax)");

@@ -123,6 +123,19 @@ __host__ __device__ __forceinline__ int64_t cixt_off(int64_t tb, int64_t blk8, i
     return (blk8 * n_tok_blocks + tb) << 5;
 }
 
+// The same for the fp8 form of that kernel (a stage is 128 hidden units): byte address of the two codes of (token t, column block blk);
+// of the 4 metadata bytes of (token t, 64 hidden units starting at column block blk8 * 8); of word 0 of the 16 offset words of
+// (token block tb, 128 hidden units number s128)
+__host__ __device__ __forceinline__ int64_t vcb8_off(int64_t t, int64_t blk, int64_t F) {
+    return (((t >> 5) * (F >> 7) + (blk >> 4)) << 10) + ((t & 31) << 5) + ((blk & 15) << 1);
+}
+__host__ __device__ __forceinline__ int64_t mcb8_off(int64_t t, int64_t blk8, int64_t F) {
+    return (((t >> 6) * (F >> 7) + (blk8 >> 1)) << 9) + ((t & 63) << 3) + ((blk8 & 1) << 2);
+}
+__host__ __device__ __forceinline__ int64_t cixt8_off(int64_t tb, int64_t s128, int64_t n_tok_blocks) {
+    return (s128 * n_tok_blocks + tb) << 6;
+}
+
 // Two survivors per 8 columns leave at most two per aligned group of four, so a V:2:8 row block is
 // also two plain 2:4 groups.  Inputs: v = the two survivors (low half first), nib = their positions
 // among the four kept columns, cw = the four kept column offsets (one per byte).  Outputs: the two

@@ -95,7 +95,7 @@ __global__ void __launch_bounds__(256) prune24_rows_fp8_kernel(const uint16_t* _
 template <bool SOFT>
 __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* __restrict__ src, int64_t R, int K, int64_t ld, float inv,
                                                               uint8_t* __restrict__ codes, uint8_t* __restrict__ meta, float* __restrict__ amax,
-                                                              uint16_t* __restrict__ codes_blk, uint16_t* __restrict__ src_q_blk, float* __restrict__ amax_src,
+                                                              uint16_t* __restrict__ codes_blk, float* __restrict__ amax_src,
                                                               uint8_t* __restrict__ meta_blk, uint8_t* __restrict__ s_q) {
     constexpr int TK = 128, TR = 64, PITCH = TR + 8;
     __shared__ __attribute__((aligned(16))) uint16_t tile[TK * PITCH];
@@ -109,19 +109,9 @@ __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* _
         uint4 w = make_uint4(0, 0, 0, 0);
         if (k0 + kk < K) w = *reinterpret_cast<const uint4*>(src + (int64_t)(k0 + kk) * ld + r0 + seg * 8);
         *reinterpret_cast<uint4*>(&tile[kk * PITCH + seg * 8]) = w;
-        if (s_q && !src_q_blk && amax_src) {    // (the magnitudes of the source, when only its transposed copy is written below)
-            m_src = __builtin_fmaxf(m_src, __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(bf2f(w.x & 0x7FFFu)), __builtin_fabsf(bf2f((w.x >> 16) & 0x7FFFu))),
-                                                            __builtin_fmaxf(__builtin_fabsf(bf2f(w.y & 0x7FFFu)), __builtin_fabsf(bf2f((w.y >> 16) & 0x7FFFu)))));
-            m_src = __builtin_fmaxf(m_src, __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(bf2f(w.z & 0x7FFFu)), __builtin_fabsf(bf2f((w.z >> 16) & 0x7FFFu))),
-                                                            __builtin_fmaxf(__builtin_fabsf(bf2f(w.w & 0x7FFFu)), __builtin_fabsf(bf2f((w.w >> 16) & 0x7FFFu)))));
-        }
-        if (src_q_blk && k0 + kk < K) {    // the unpruned source itself, quantised, in its own orientation [K rows, R codes] (blocked pairs)
-            const float f[8] = {bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16),
-                                bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16)};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) m_src = __builtin_fmaxf(m_src, __builtin_fabsf(f[e]));
-            *reinterpret_cast<uint2*>(src_q_blk + blk_off(k0 + kk, (r0 + seg * 8) / 2, R / 64)) =
-                make_uint2(enc2(f[0], f[1], inv) | (enc2(f[2], f[3], inv) << 16), enc2(f[4], f[5], inv) | (enc2(f[6], f[7], inv) << 16));
+        if (s_q && amax_src) {      // the magnitudes of the source (its dense use, written below as S itself quantised, shares the scale)
+            m_src = __builtin_fmaxf(m_src, __builtin_fmaxf(__builtin_fmaxf(bf2f(w.x & 0x7FFFu), bf2f((w.x >> 16) & 0x7FFFu)), __builtin_fmaxf(bf2f(w.y & 0x7FFFu), bf2f((w.y >> 16) & 0x7FFFu))));
+            m_src = __builtin_fmaxf(m_src, __builtin_fmaxf(__builtin_fmaxf(bf2f(w.z & 0x7FFFu), bf2f((w.z >> 16) & 0x7FFFu)), __builtin_fmaxf(bf2f(w.w & 0x7FFFu), bf2f((w.w >> 16) & 0x7FFFu))));
         }
     }
     __syncthreads();
@@ -148,14 +138,14 @@ __global__ void __launch_bounds__(256) prune24_cols_fp8_kernel(const uint16_t* _
         }
         if (codes_blk) *reinterpret_cast<uint4*>(codes_blk + blk_off(r, (k0 + 32 * q) / 4, K / 128)) = make_uint4(oc[0], oc[1], oc[2], oc[3]);   // 16 codes = 8 pairs
         if (meta_blk) *reinterpret_cast<uint32_t*>(meta_blk + m8blk_off(r, k0 + 32 * q, K / 128)) = mbytes;
-        if (s_q) {          // the unpruned logical matrix S itself, quantised, row-major [R, K] codes (rows of it are gathered by eq. (3) for M >= 16)
+        if (s_q) {          // the unpruned logical matrix S itself, quantised, row-major [R, K] codes (eq. (3) contracts its kept rows)
             uint4* d = reinterpret_cast<uint4*>(s_q + r * K + k0 + 32 * q);
             d[0] = make_uint4(sq[0], sq[1], sq[2], sq[3]);
             d[1] = make_uint4(sq[4], sq[5], sq[6], sq[7]);
         }
     }
     note_amax(amax, m);
-    if (amax_src) note_amax_slots(amax_src, m_src);      // over every element of the source (its dense use shares the scale)
+    if (amax_src) note_amax_slots(amax_src, m_src);      // over every element of the source
 }
 
 // eq. (2) + V:N:M compression with fp8 values: the structure of sqrelu_vnm_compress_m_kernel (vnm_general.hip): one workgroup =
@@ -301,14 +291,11 @@ __global__ void __launch_bounds__(256) quantize_fp8_blocked_kernel(const uint16_
 }
 
 // [R, C] bf16 -> codes of the transposed matrix [C, R] in the blocked pair layout; 64 x 64 tiles through LDS.  While the tile is in
-// registers the same pass can also write (EXTRA 1) the codes in the source's own orientation, blocked (X, dY of the fp8 step with fp8
-// weight gradients), or (EXTRA 2) the 2:4 pruning of the rows (Section 2.2, HARD / SOFT): canonical codes [R, C/2] + metadata [R, C/8] +
-// the pruned codes blocked (W1 of the fp8 step: pruned for eq. (1), dense and transposed for eq. (7), one read).
-template <int EXTRA, bool SOFT>
+// registers the same pass can also write (EXTRA) the codes in the source's own orientation, blocked (X, dY of the fp8 step with fp8
+// weight gradients).
+template <bool EXTRA>
 __global__ void __launch_bounds__(256) transpose_quantize_fp8_blocked_kernel(const uint16_t* __restrict__ src, int64_t R, int64_t C, int64_t ld, float inv,
-                                                                            uint16_t* __restrict__ out, float* __restrict__ amax, uint16_t* __restrict__ out_same,
-                                                                            uint8_t* __restrict__ p_codes, uint8_t* __restrict__ p_meta, uint16_t* __restrict__ p_blk,
-                                                                            uint8_t* __restrict__ p_mblk) {
+                                                                            uint16_t* __restrict__ out, float* __restrict__ amax, uint16_t* __restrict__ out_same) {
     __shared__ uint16_t tile[64][64 + 2];
     const int tid = threadIdx.x;
     const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
@@ -318,24 +305,10 @@ __global__ void __launch_bounds__(256) transpose_quantize_fp8_blocked_kernel(con
         const uint4 w = *reinterpret_cast<const uint4*>(src + (r0 + r) * ld + c0 + seg * 8);
         uint32_t* d = reinterpret_cast<uint32_t*>(&tile[r][seg * 8]);
         d[0] = w.x; d[1] = w.y; d[2] = w.z; d[3] = w.w;
-        if (EXTRA == 1)
+        if (EXTRA)
             *reinterpret_cast<uint2*>(out_same + blk_off(r0 + r, (c0 + seg * 8) / 2, C / 64)) =
                 make_uint2(enc2(bf2f(w.x & 0xFFFFu), bf2f(w.x >> 16), inv) | (enc2(bf2f(w.y & 0xFFFFu), bf2f(w.y >> 16), inv) << 16),
                            enc2(bf2f(w.z & 0xFFFFu), bf2f(w.z >> 16), inv) | (enc2(bf2f(w.w & 0xFFFFu), bf2f(w.w >> 16), inv) << 16));
-        if (EXTRA == 2) {
-            uint32_t n0, n1;
-            float a, b, d2, e;
-            select24_f32<SOFT>(w.x & 0xFFFFu, w.x >> 16, w.y & 0xFFFFu, w.y >> 16, n0, a, b);
-            select24_f32<SOFT>(w.z & 0xFFFFu, w.z >> 16, w.w & 0xFFFFu, w.w >> 16, n1, d2, e);
-            const uint32_t q4 = enc2(a, b, inv) | (enc2(d2, e, inv) << 16);
-            const int64_t cc = (c0 + seg * 8) / 8;                  // chunk of 8 columns inside the row
-            if (p_codes) {      // (lean form of the step: no canonical copy)
-                *reinterpret_cast<uint32_t*>(p_codes + (r0 + r) * (C / 2) + cc * 4) = q4;
-                p_meta[(r0 + r) * (C / 8) + cc] = (uint8_t)(n0 | (n1 << 4));
-            }
-            p_mblk[m8blk_off(r0 + r, cc * 8, C / 128)] = (uint8_t)(n0 | (n1 << 4));
-            *reinterpret_cast<uint32_t*>(p_blk + blk_off(r0 + r, cc * 2, C / 128)) = q4;
-        }
     }
     __syncthreads();
     float m = 0.0f;
@@ -380,16 +353,12 @@ hipError_t launch_amax_finish(const float* slots, int n, float* out, hipStream_t
 }
 
 hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s, float* amax,
-                                                 uint8_t* out_same_blk, int prune_mode, uint8_t* p_codes, uint8_t* p_meta, uint8_t* p_blk, uint8_t* p_mblk) {
-    if (C % 64 != 0 || R % 64 != 0 || (out_same_blk && p_blk) || (p_blk && (!p_mblk || C % 128 != 0)) || (p_codes && (!p_meta || !p_blk))) return hipErrorInvalidValue;
+                                                 uint8_t* out_same_blk) {
+    if (C % 64 != 0 || R % 64 != 0) return hipErrorInvalidValue;
     dim3 grid((unsigned)(C / 64), (unsigned)(R / 64));
     uint16_t* o = reinterpret_cast<uint16_t*>(out_t_blk);
-#define SFFN_TQ(E, SOFT) hipLaunchKernelGGL((transpose_quantize_fp8_blocked_kernel<E, SOFT>), grid, dim3(256), 0, s, src, R, C, ld, inv, o, amax, \
-                                           reinterpret_cast<uint16_t*>(out_same_blk), p_codes, p_meta, reinterpret_cast<uint16_t*>(p_blk), p_mblk)
-    if (p_blk) { if (prune_mode == 0) SFFN_TQ(2, false); else SFFN_TQ(2, true); }
-    else if (out_same_blk) SFFN_TQ(1, false);
-    else SFFN_TQ(0, false);
-#undef SFFN_TQ
+    if (out_same_blk) hipLaunchKernelGGL((transpose_quantize_fp8_blocked_kernel<true>), grid, dim3(256), 0, s, src, R, C, ld, inv, o, amax, reinterpret_cast<uint16_t*>(out_same_blk));
+    else              hipLaunchKernelGGL((transpose_quantize_fp8_blocked_kernel<false>), grid, dim3(256), 0, s, src, R, C, ld, inv, o, amax, (uint16_t*)nullptr);
     return hipGetLastError();
 }
 
@@ -400,22 +369,7 @@ hipError_t launch_quantize_fp8(const uint16_t* src, int64_t n, float inv, uint8_
 }
 
 static hipError_t launch_prune24_fp8_impl(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                          float* amax, uint16_t* blk, uint16_t* srcq, float* amax_src, uint8_t* mblk, hipStream_t s, uint8_t* s_q = nullptr);
-
-hipError_t launch_prune24_fp8(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                              float* amax, hipStream_t s) {
-    return launch_prune24_fp8_impl(src, R, K, ld, trans, mode, inv, codes, meta, amax, nullptr, nullptr, nullptr, nullptr, s);
-}
-
-hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                   uint8_t* codes_blk, uint8_t* meta_blk, hipStream_t s, uint8_t* src_q_blk, float* amax_src, uint8_t* s_q) {
-    if (K % 128 != 0 || !meta_blk || (src_q_blk && (!trans || R % 64 != 0 || K % 16 != 0)) || (src_q_blk && s_q)) return hipErrorInvalidValue;   // a block row holds whole 64-byte pieces of the K / 2 codes per row
-    return launch_prune24_fp8_impl(src, R, K, ld, trans, mode, inv, codes, meta, nullptr, reinterpret_cast<uint16_t*>(codes_blk),
-                                   reinterpret_cast<uint16_t*>(src_q_blk), (src_q_blk || s_q) ? amax_src : nullptr, meta_blk, s, s_q);
-}
-
-static hipError_t launch_prune24_fp8_impl(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                          float* amax, uint16_t* blk, uint16_t* srcq, float* amax_src, uint8_t* mblk, hipStream_t s, uint8_t* s_q) {
+                                          float* amax, uint16_t* blk, float* amax_src, uint8_t* mblk, uint8_t* s_q, hipStream_t s) {
     if (!trans) {
         const int64_t nchunks = R * (K / 8);
         const unsigned grid = (unsigned)((nchunks + 255) / 256);
@@ -423,10 +377,21 @@ static hipError_t launch_prune24_fp8_impl(const uint16_t* src, int64_t R, int64_
         else           hipLaunchKernelGGL((prune24_rows_fp8_kernel<true>), dim3(grid), dim3(256), 0, s, src, nchunks, (int)(K / 8), ld, inv, codes, meta, amax, blk, mblk, s_q, amax_src);
     } else {
         dim3 grid((unsigned)(R / 64), (unsigned)((K + 127) / 128));
-        if (mode == 0) hipLaunchKernelGGL((prune24_cols_fp8_kernel<false>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq, amax_src, mblk, s_q);
-        else           hipLaunchKernelGGL((prune24_cols_fp8_kernel<true>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, srcq, amax_src, mblk, s_q);
+        if (mode == 0) hipLaunchKernelGGL((prune24_cols_fp8_kernel<false>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, amax_src, mblk, s_q);
+        else           hipLaunchKernelGGL((prune24_cols_fp8_kernel<true>), grid, dim3(256), 0, s, src, R, (int)K, ld, inv, codes, meta, amax, blk, amax_src, mblk, s_q);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_prune24_fp8(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
+                              float* amax, hipStream_t s) {
+    return launch_prune24_fp8_impl(src, R, K, ld, trans, mode, inv, codes, meta, amax, nullptr, nullptr, nullptr, nullptr, s);
+}
+
+hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
+                                   uint8_t* codes_blk, uint8_t* meta_blk, hipStream_t s, float* amax_src, uint8_t* s_q) {
+    if (K % 128 != 0 || R % 64 != 0 || !codes_blk || !meta_blk || !s_q) return hipErrorInvalidValue;   // a block row holds whole 64-byte pieces of the K / 2 codes per row
+    return launch_prune24_fp8_impl(src, R, K, ld, trans, mode, inv, codes, meta, nullptr, reinterpret_cast<uint16_t*>(codes_blk), amax_src, meta_blk, s_q, s);
 }
 
 hipError_t launch_sqrelu_vnm_compress_fp8(const uint16_t* y1, int64_t T, int64_t F, int M, float inv, uint8_t* codes, uint8_t* meta, uint8_t* colidx,

@@ -616,6 +616,13 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         ep.kmask[(int64_t)(t0 >> 6) * nblk + (f0 >> 3) + (lane >> 3)] = (uint8_t)bits;
                     }
                     cw = (uint32_t)__shfl((int)mine, bl * 8, 64);
+                    if (FP8 && ep.cixt) {       // fp8 form: 16 words per 128 hidden units, word q = (h, p); this half of them (64 hidden units) fills two bytes
+                        const int q = lane & 15, hq = q >> 3, pq = q & 7, hf = (f0 >> 6) & 1;
+                        const uint32_t b0 = ((uint32_t)__shfl((int)mine, (4 * hq + (pq >> 2)) * 8, 64) >> (8 * (pq & 3))) & 0xFFu;
+                        const uint32_t b1 = ((uint32_t)__shfl((int)mine, (4 * hq + 2 + (pq >> 2)) * 8, 64) >> (8 * (pq & 3))) & 0xFFu;
+                        if (valid && lane < 16)
+                            *reinterpret_cast<uint16_t*>(ep.cixt + cixt8_off(t0 >> 6, f0 >> 7, tok_ld >> 6) + q * 4 + 2 * hf) = (uint16_t)(b0 | (b1 << 8));
+                    }
                     if (!FP8 && ep.cixt) {      // the same offsets regrouped for the transposing reads of gemm_vnm8.hip: word q = (h, r), byte j
                         const int q = lane & 7, hq = q >> 2, rq = q & 3;
                         uint32_t dw = 0;
@@ -631,11 +638,10 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                 uint32_t* vals_p = reinterpret_cast<uint32_t*>(ep.vals) + ((int64_t)(t0 + (lane >> 3)) * (F / 4) + blk_g * 2) / 2;
                 uint32_t* kept_p = reinterpret_cast<uint32_t*>(ep.ykept) + ykept_off(t0 + (lane >> 3), blk_g, F);
                 uint8_t* meta_p = ep.meta + (int64_t)(t0 + (lane >> 3)) * (F / 16) + (blk_g >> 1);
-                // fp8: v24 holds pairs of codes (4 codes per block = 2 pairs), m24 is in the fp8 metadata units
-                uint16_t* v24_p = FP8 ? ep.v24 + blk_off(t0 + (lane >> 3), blk_g * 2, F / 128) : ep.v24 + blk_off(t0 + (lane >> 3), blk_g * 4, F / 64);
-                uint8_t* m24_p = FP8 ? ep.m24 : ep.m24 + mblk_off(t0 + (lane >> 3), blk_g * 8, F / 64);      // (fp8: address per sweep, below)
-                uint32_t* vcb_p = FP8 ? nullptr : reinterpret_cast<uint32_t*>(ep.vcb + vcb_off(t0 + (lane >> 3), blk_g, F));    // sweep it: + (it / 4) 32-token groups + 8 (it % 4) tokens
-                uint8_t* mcb_p = FP8 ? nullptr : ep.mcb + mcb_off(t0 + (lane >> 3), f0 >> 6, F);                                // + 8 tokens per sweep = + 32 bytes
+                // operands of eq. (3) / eq. (7) on the V:2:8 kernel (gemm_vnm8.hip); sweep it: + (it / 4) 32-token groups + 8 (it % 4) tokens
+                uint32_t* vcb_p = FP8 ? nullptr : reinterpret_cast<uint32_t*>(ep.vcb + vcb_off(t0 + (lane >> 3), blk_g, F));
+                uint8_t* vcb8_p = FP8 ? reinterpret_cast<uint8_t*>(ep.vcb) + vcb8_off(t0 + (lane >> 3), blk_g, F) : nullptr;   // (the lane of block 0 stores its row's 8 pairs of codes)
+                uint8_t* mcb_p = FP8 ? ep.mcb + mcb8_off(t0 + (lane >> 3), f0 >> 6, F) : ep.mcb + mcb_off(t0 + (lane >> 3), f0 >> 6, F);
                 const uint32_t c0 = (cw & 0xFFu) * 2, c1 = ((cw >> 8) & 0xFFu) * 2, c2 = ((cw >> 16) & 0xFFu) * 2, c3 = (cw >> 24) * 2;
                 uint32_t pre_m[8], pre_y[8];                                // EPI 2: saved metadata and y1 of the 8 sweeps, fetched together
                 if (EPI == 2 && valid) {
@@ -672,7 +678,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             mw |= row_shl<2>(mw) << 8;
                             mw |= row_shl<4>(mw) << 16;
                             if (bl == 0) *reinterpret_cast<uint32_t*>(meta_p + (int64_t)it * 8 * (F / 16)) = mw;
-                            if (!FP8 && ep.mcb && bl == 0) *reinterpret_cast<uint32_t*>(mcb_p + it * 32) = mw;
+                            if (ep.mcb && bl == 0) *reinterpret_cast<uint32_t*>(mcb_p + it * (FP8 ? 64 : 32)) = mw;
                         } else {
                             const uint32_t mb = pre_m[it];
                             const uint32_t yk = pre_y[it];
@@ -686,23 +692,12 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                             if (ep.vals) vals_p[(int64_t)it * 8 * (F / 8)] = v;
                         }
                         if (FP8) vmax = __builtin_fmaxf(vmax, __builtin_fmaxf(__builtin_fabsf(bf2f(v & 0xFFFFu)), __builtin_fabsf(bf2f(v >> 16))));
-                        if (!FP8 && ep.vcb) vcb_p[(int64_t)(it >> 2) * (F >> 6) * 256 + (it & 3) * 64] = v;     // operand of eq. (3) / eq. (7) on the V:2:8 kernel
-                        // the same block as two plain 2:4 groups (blocked operand of eq. (3) / eq. (7))
-                        if (ep.v24) {       // (not wanted when eq. (7) gathers rows from the canonical arrays)
-                            uint32_t a24, b24, mb8;
-                            vnm_block_to_24(v, nib, cw, a24, b24, mb8);
-                            if (FP8) {      // the survivors' codes (an empty slot is code 0 = +0); four blocks' metadata bytes in one store
-                                const uint32_t qa = fp8_enc2(bf2f(a24 & 0xFFFFu), bf2f(a24 >> 16), ep.inv_out);
-                                const uint32_t qb = fp8_enc2(bf2f(b24 & 0xFFFFu), bf2f(b24 >> 16), ep.inv_out);
-                                *reinterpret_cast<uint32_t*>(v24_p + (int64_t)(it >> 1) * (F / 128) * 512 + (it & 1) * 256) = qa | (qb << 16);
-                                uint32_t m4 = mb8 | (row_shl<1>(mb8) << 8);
-                                m4 |= row_shl<2>(m4) << 16;
-                                if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(m24_p + m8blk_off(t0 + t, blk_g * 8, F / 128)) = m4;
-                            } else {
-                            const uint32_t m2 = mb8 | (row_shl<1>(mb8) << 8);     // two column blocks = 16 k = one lane's half-word of a unit
-                            *reinterpret_cast<uint2*>(v24_p + (int64_t)(it >> 1) * (F / 64) * 512 + (it & 1) * 256) = make_uint2(a24, b24);
-                            if ((lane & 1) == 0) *reinterpret_cast<uint16_t*>(m24_p + (int64_t)(it >> 2) * (F / 64) * 256 + (it & 3) * 32) = (uint16_t)m2;
-                            }
+                        if (!FP8 && ep.vcb) vcb_p[(int64_t)(it >> 2) * (F >> 6) * 256 + (it & 3) * 64] = v;
+                        if (FP8 && ep.vcb) {    // the survivors' codes: the row's 8 pairs gathered into the lane of block 0, one 16-byte store
+                            const uint32_t q2 = fp8_enc2(bf2f(v & 0xFFFFu), bf2f(v >> 16), ep.inv_out);
+                            const uint32_t w2 = q2 | (row_shl<1>(q2) << 16);
+                            const uint4 w8 = make_uint4(w2, row_shl<2>(w2), row_shl<4>(w2), row_shl<6>(w2));
+                            if (bl == 0) *reinterpret_cast<uint4*>(vcb8_p + (int64_t)(it >> 2) * (F >> 7) * 1024 + (it & 3) * 256) = w8;
                         }
                         // transposed tile for the weight-gradient GEMM, compacted to the block's four kept hidden units:
                         // row = 4 * block + position among the kept units, column = token
@@ -818,13 +813,13 @@ hipError_t launch_spmm24_fp8(const uint8_t* a_codes, const uint8_t* a_meta, cons
 
 hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* Bq, const float* bias, float alpha, int64_t Ra,
                                    int64_t Rb, int64_t K, uint16_t* out, int64_t ldo, const VnmEpilogue* ep, hipStream_t s, const GemmGroup* grp) {
-    if (K % 128 != 0 || (ep && ep->mode != 1 && ep->mode != 2 && ep->mode != 5 && ep->mode != 6)) return hipErrorInvalidValue;
-    if (ep && ep->mode >= 5 && (ep->logM < 4 || ep->logM > 6)) return hipErrorInvalidValue;
+    if (K % 128 != 0 || !ep || (ep->mode != 1 && ep->mode != 2 && ep->mode != 5 && ep->mode != 6)) return hipErrorInvalidValue;
+    if (ep->mode >= 5 && (ep->logM < 4 || ep->logM > 6)) return hipErrorInvalidValue;
     const int tiles_m = (int)((Ra + 255) / 256), tiles_n = (int)((Rb + 255) / 256);
-    const VnmEpilogue e = ep ? *ep : VnmEpilogue();
+    const VnmEpilogue e = *ep;
     const GemmGroup g = grp ? *grp : GemmGroup();
-    // grouped: the tokens are the j rows under an epilogue (role 1: A = the expert's packed weights), the i rows otherwise (role 0)
-    if (g.n && (g.n > GemmGroup::kMaxExperts || g.role != (ep ? 1 : 0) || g.seg_dev)) return hipErrorInvalidValue;
+    // grouped: the tokens are the j rows (role 1: A = the expert's packed weights)
+    if (g.n && (g.n > GemmGroup::kMaxExperts || g.role != 1 || g.seg_dev)) return hipErrorInvalidValue;
     const unsigned tiles = grid_tiles(tiles_m, tiles_n, g);
     if (tiles == 0) return hipSuccess;
     dim3 grid(tiles);
@@ -832,8 +827,7 @@ hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta
     const uint16_t* b = reinterpret_cast<const uint16_t*>(Bq);
 #define SFFN_F8(ICONTIG, E) hipLaunchKernelGGL((gemm_nt_v2_kernel<true, ICONTIG, E, true, true>), grid, dim3(512), 0, s, a, a_meta, b, bias, (int)Ra, (int)Rb, \
                                               (int)(K / 2), out, ldo, tiles_m, tiles_n, e, g, alpha)
-    if (!ep) SFFN_F8(false, 0);
-    else if (ep->mode == 1) SFFN_F8(true, 1);
+    if (ep->mode == 1) SFFN_F8(true, 1);
     else if (ep->mode == 2) SFFN_F8(true, 2);
     else if (ep->mode == 5) { if (ep->logM == 4) SFFN_F8(true, 20); else if (ep->logM == 5) SFFN_F8(true, 21); else SFFN_F8(true, 22); }
     else                    { if (ep->logM == 4) SFFN_F8(true, 36); else if (ep->logM == 5) SFFN_F8(true, 37); else SFFN_F8(true, 38); }

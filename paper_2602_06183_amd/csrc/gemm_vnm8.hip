@@ -19,30 +19,57 @@
 //   offsets   [F / 64][T / 64][8 words]                word (h, r), byte j = kept column r of column block 4 (j / 2) + j % 2 + 2 h of the
 //                                                      stage: the four rows that lane (h = lane / 32, r = (lane % 16) / 4) addresses in read j
 // A stage = 64 hidden units = 32 k' = one matrix instruction step per fragment pair; 3 stages of 41.25 KB.
+//
+// FP8 (the fp8 step): the same kernel on E4M3 codes with v_smfmac_f32_32x32x64_fp8_fp8, out = bf16(alpha * sum).  A stage is 128 hidden
+// units = 64 k' (the instruction's K): the slab is 128 rows x 256 bytes, the survivors' codes fill the same 32 bytes per token and stage,
+// the metadata 8 bytes.  The B fragments are read with ds_read_b64_tr_b8 (inside a group of 16 lanes, lane s supplies 8 consecutive bytes of
+// row s / 2, lane l receives byte l of those 8 rows), so a read covers the kept rows of TWO column blocks; the offsets unit of a (128 hidden
+// units, token block) is 16 words: word (h, p), byte j = kept column p % 4 of column block 8 (j / 2) + 4 h + 2 (j % 2) + p / 4.  The 32-byte
+// pieces of a slab row are swizzled by f % 8.
 #include "common.hpp"
 #include "kernels.hpp"
 #include "lds_dma.hpp"
+
+// Tile rows per band of the workgroup -> tile map (see SFFN_TILE_GROUP in common.hpp).  A tile fetches four times as many bytes of Wk as of
+// the packed activation, so the 32 tiles that an XCD runs at a time should share few column slabs of Wk: tall bands (measured at
+// T = D = 8192, F = 28672: 1.49 / 1.42 / 1.38 / 1.36 ms per launch with 2 / 4 / 8 / 16 tile rows per band).
+#ifndef SFFN_VNM8_GROUP
+#define SFFN_VNM8_GROUP 16
+#endif
 
 namespace sffn {
 
 namespace {
 
 constexpr int kStages = 3;
-constexpr int kB = 64 * 512, kA = 256 * 32, kMt = 256 * 4, kC = 256;
-constexpr int kStage = kB + kA + kMt + kC;           // 42240 bytes
+template <bool FP8>
+struct G {
+    static constexpr int SLAB = FP8 ? 128 : 64;         // hidden units per stage
+    static constexpr int kB = 64 * 512;                 // slab bytes (64 x 512 or 128 x 256)
+    static constexpr int kA = 256 * 32;
+    static constexpr int kMt = FP8 ? 256 * 8 : 256 * 4;
+    static constexpr int kC = 256;
+    static constexpr int kStage = kB + kA + kMt + kC;   // 42240 / 43264 bytes
+};
 constexpr int kLoads = 4 + 1 + 1 + 1;                // per wave per stage
 // Measurement switches (wrong results by design): SFFN_VNM8_NO_MFMA leaves the matrix instructions out, SFFN_VNM8_NO_DMA the loads after the
 // prologue, SFFN_VNM8_NO_BREAD the transposing reads of the B fragments.
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) v2i lds_v2i;
 
 }  // namespace
 
+// Wk / ldw: bf16 elements, or (FP8) code bytes
+template <bool FP8>
 __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restrict__ vcb, const uint8_t* __restrict__ mcb,
-                                                       const uint8_t* __restrict__ cixt, const uint16_t* __restrict__ Wk, int ldw,
+                                                       const uint8_t* __restrict__ cixt, const uint8_t* __restrict__ Wk, int ldw,
                                                        int Ra, int N, int F, int Ttot, uint16_t* __restrict__ out, int64_t ldo,
-                                                       int tiles_m, int tiles_n, GemmGroup grp) {
+                                                       int tiles_m, int tiles_n, GemmGroup grp, float alpha) {
+    constexpr int kB = G<FP8>::kB, kA = G<FP8>::kA, kMt = G<FP8>::kMt, kStage = G<FP8>::kStage;
+    constexpr int ES = FP8 ? 1 : 2;                      // bytes per element of Wk
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kStages * kStage];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -65,34 +92,42 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
         }
         if (e == grp.n) return;
         tiles_m = cnt / tiles_n; i_base = grp.seg[e]; Ra = grp.seg[e + 1];
-        Wk += e * grp.b_stride;
+        Wk += (int64_t)e * grp.b_stride * ES;
     }
     int tm, tn;
     {
-        constexpr int GROUP = SFFN_TILE_GROUP;
+        constexpr int GROUP = SFFN_VNM8_GROUP;
         const int width = GROUP * tiles_n, group = L / width, first = group * GROUP;
         const int gsz = (tiles_m - first) < GROUP ? (tiles_m - first) : GROUP;
         tm = first + (L % width) % gsz;
         tn = (L % width) / gsz;
     }
     const int i0 = i_base + tm * 256, n0 = tn * 256;
-    const int KS = F >> 6;                               // stages = 64-wide slabs of hidden units
+    const int KS = F / G<FP8>::SLAB;                     // stages = slabs of 64 (128) hidden units
     const int NTB = Ttot >> 6;
 
     // ---- DMA sources (wave-uniform 64-bit base + 32-bit per-lane offset).  Token groups past the end of the operand are clamped into it:
     //      they only feed outputs that are never stored. ----------------------------------------------------------------------------------
     // B: load i of wave w (i = 0..3) brings slab rows 2 (4 w + i) + lane / 32; lane % 32 is the 16-byte slot inside the 512-byte row and
-    // fetches the chunk whose 64-byte piece the swizzle puts there.  Chunks past the right edge of Wk are redirected into the first 64 columns.
+    // fetches the chunk whose 64-byte piece the swizzle puts there (FP8: rows 4 (4 w + i) + lane / 16 of 256 bytes, 32-byte pieces).
+    // Chunks past the right edge of Wk are redirected into the first 64 columns.
     const uint64_t w_base = uniform64(Wk);
     uint32_t b_lane[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int row = 2 * (4 * wave + i) + lh, slot = l32;
-        int c = (((slot >> 2) ^ (row & 7)) << 2) | (slot & 3);
-        if (n0 + c * 8 >= N) c &= 7;
-        b_lane[i] = (uint32_t)row * (uint32_t)ldw * 2u + (uint32_t)(n0 + c * 8) * 2u;
+        if (FP8) {
+            const int row = 4 * (4 * wave + i) + (lane >> 4), slot = lane & 15;
+            int c = (((slot >> 1) ^ (row & 7)) << 1) | (slot & 1);
+            if (n0 + c * 16 >= N) c &= 3;
+            b_lane[i] = (uint32_t)row * (uint32_t)ldw + (uint32_t)(n0 + c * 16);
+        } else {
+            const int row = 2 * (4 * wave + i) + lh, slot = l32;
+            int c = (((slot >> 2) ^ (row & 7)) << 2) | (slot & 3);
+            if (n0 + c * 8 >= N) c &= 7;
+            b_lane[i] = (uint32_t)row * (uint32_t)ldw * 2u + (uint32_t)(n0 + c * 8) * 2u;
+        }
     }
-    const uint32_t b_kstep = 64u * (uint32_t)ldw * 2u;
+    const uint32_t b_kstep = (uint32_t)G<FP8>::SLAB * (uint32_t)ldw * ES;
     uint64_t a_base, m_base, c_base;
     uint32_t a_lane, m_lane, c_lane;
     {
@@ -101,17 +136,25 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
         a_base = uniform64(vcb + (int64_t)g32 * KS * 512);
         const int row = lane >> 1, slot = lane & 1;
         a_lane = (uint32_t)(row * 32 + ((slot ^ ((row >> 3) & 1)) << 4));
-        int g64 = (i0 >> 6) + (wave & 3);                // waves w and w + 4 fetch the same 64 tokens' metadata
-        g64 = g64 < NTB ? g64 : NTB - 1;
-        m_base = uniform64(mcb + (int64_t)g64 * KS * 256);
+        if (FP8) {          // 8 bytes per token and stage: the wave's own 32 tokens, 256 bytes of the 512-byte unit of their token block
+            int g64 = (i0 >> 6) + (wave >> 1);
+            g64 = g64 < NTB ? g64 : NTB - 1;
+            m_base = uniform64(mcb + (int64_t)g64 * KS * 512 + (wave & 1) * 256);
+        } else {            // 4 bytes: waves w and w + 4 fetch the same 64 tokens' metadata
+            int g64 = (i0 >> 6) + (wave & 3);
+            g64 = g64 < NTB ? g64 : NTB - 1;
+            m_base = uniform64(mcb + (int64_t)g64 * KS * 256);
+        }
         m_lane = lane * 4;
-        // offsets of the tile's four token blocks: 4 x 32 bytes, every wave fetches all of them (lanes 32-63 repeat lanes 0-31)
-        int tb = (i0 >> 6) + (l32 >> 3);
+        // offsets of the tile's four token blocks: 4 x 32 (FP8: 4 x 64) bytes, every wave fetches all of them
+        const int words = FP8 ? 16 : 8;
+        int tb = (i0 >> 6) + (FP8 ? (lane >> 4) : (l32 >> 3));
         tb = tb < NTB ? tb : NTB - 1;
         c_base = uniform64(cixt);
-        c_lane = (uint32_t)(tb * 32 + (lane & 7) * 4);
+        c_lane = (uint32_t)(tb * words * 4 + (lane & (words - 1)) * 4);
     }
-    const uint32_t c_kstep = (uint32_t)NTB * 32u;
+    const uint32_t c_kstep = (uint32_t)NTB * (FP8 ? 64u : 32u);
+    constexpr uint32_t m_kstep = FP8 ? 512u : 256u;
     auto issue_half = [&](int kt, int stage, int h) {
 #ifdef SFFN_VNM8_NO_DMA
         if (kt >= kStages) return;
@@ -128,7 +171,7 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
         } else {
             dma16(w_base, b_lane[2] + (uint32_t)kt * b_kstep, sb + (4 * wave + 2) * 1024);
             dma16(w_base, b_lane[3] + (uint32_t)kt * b_kstep, sb + (4 * wave + 3) * 1024);
-            dma4(m_base, m_lane + (uint32_t)kt * 256u, sm + (wave & 3) * 256);
+            dma4(m_base, m_lane + (uint32_t)kt * m_kstep, sm + (FP8 ? wave : (wave & 3)) * 256);
         }
     };
     auto issue = [&](int kt, int stage) { issue_half(kt, stage, 0); issue_half(kt, stage, 1); };
@@ -141,16 +184,19 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
     for (int a = 0; a < 2; ++a) {
         const int row = tbw * 64 + a * 32 + l32;
         a_off[a] = kB + row * 32 + ((lh ^ ((row >> 3) & 1)) << 4);
-        m_off[a] = kB + kA + row * 4 + 2 * lh;
+        m_off[a] = kB + kA + (FP8 ? row * 8 + 4 * lh : row * 4 + 2 * lh);
     }
-    // transpose read j of fragment fn: slab row = 8 cb(j) + c with cb(j) = 4 (j / 2) + j % 2 + 2 h and c = byte j of the lane's offsets word;
-    // byte address = row * 512 + ((4 nh + fn) ^ c) * 64 + 32 (column half) + 8 (lane % 4)
-    const int r4 = (lane & 15) >> 2, g = lane >> 4;
-    const int c_off = kB + kA + kMt + 32 * tbw + (lh * 4 + r4) * 4;
-    const int b_fix = ((g & 1) << 5) + ((lane & 3) << 3);
+    // bf16: transpose read j of fragment fn: slab row = 8 cb(j) + c with cb(j) = 4 (j / 2) + j % 2 + 2 h and c = byte j of the lane's offsets
+    // word; byte address = row * 512 + ((4 nh + fn) ^ c) * 64 + 32 (column half) + 8 (lane % 4)
+    // FP8: the lane addresses row p = (lane % 16) / 2 of the read's 8: cb(j) = 8 (j / 2) + 4 h + 2 (j % 2) + p / 4, c = byte j of word (h, p);
+    // byte address = row * 256 + ((4 nh + fn) ^ c) * 32 + 16 (column half) + 8 (lane % 2)
+    const int r4 = (lane & 15) >> 2, p8 = (lane & 15) >> 1, g = lane >> 4;
+    const int c_off = kB + kA + kMt + (FP8 ? 64 * tbw + (lh * 8 + p8) * 4 : 32 * tbw + (lh * 4 + r4) * 4);
+    const int b_fix = FP8 ? ((g & 1) << 4) + ((lane & 1) << 3) : ((g & 1) << 5) + ((lane & 3) << 3);
     int b_cb[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) b_cb[j] = (4 * (j >> 1) + (j & 1) + 2 * lh) * 8 * 512 + b_fix;
+    for (int j = 0; j < 4; ++j)
+        b_cb[j] = FP8 ? (8 * (j >> 1) + 4 * lh + 2 * (j & 1) + (p8 >> 2)) * 8 * 256 + b_fix : (4 * (j >> 1) + (j & 1) + 2 * lh) * 8 * 512 + b_fix;
 
     f32x16 acc[2][4];
 #pragma unroll
@@ -162,14 +208,14 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
 
     // The stage's fragments in two halves: P = both A fragments, the offsets word and B fragments 0, 1; Q = B fragments 2, 3 (the A
     // fragments of P stay live until Q's matrix instructions, so A is double-buffered by stage parity)
-    struct BPair { union { s16x4 q[4]; bf16x16 v; } b[2]; };
+    struct BPair { union { s16x4 q[4]; v2i q8[4]; bf16x16 v; i32x8 v8; } b[2]; };
     struct AFrags { Frag8 a[2]; int idx[2]; uint32_t cw; };
     auto read_a = [&](AFrags& f, const unsigned char* st) {
         f.cw = *reinterpret_cast<const uint32_t*>(st + c_off);
 #pragma unroll
         for (int a2 = 0; a2 < 2; ++a2) {
             f.a[a2].u = *reinterpret_cast<const uint4*>(st + a_off[a2]);
-            f.idx[a2] = *reinterpret_cast<const uint16_t*>(st + m_off[a2]);
+            f.idx[a2] = FP8 ? (int)*reinterpret_cast<const uint32_t*>(st + m_off[a2]) : (int)*reinterpret_cast<const uint16_t*>(st + m_off[a2]);
         }
     };
     auto read_b = [&](BPair& f, const unsigned char* st, uint32_t cw, int half) {
@@ -180,9 +226,15 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t c = (cw >> (8 * j)) & 7u;
-            const uint32_t addr = (uint32_t)b_cb[j] + c * 512u + (((4u * nh + 2u * half) ^ c) << 6);
-            f.b[0].q[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(st + addr));
-            f.b[1].q[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(st + (addr ^ 64u)));
+            if (FP8) {
+                const uint32_t addr = (uint32_t)b_cb[j] + c * 256u + (((4u * nh + 2u * half) ^ c) << 5);
+                f.b[0].q8[j] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i*)(st + addr));
+                f.b[1].q8[j] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i*)(st + (addr ^ 32u)));
+            } else {
+                const uint32_t addr = (uint32_t)b_cb[j] + c * 512u + (((4u * nh + 2u * half) ^ c) << 6);
+                f.b[0].q[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(st + addr));
+                f.b[1].q[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(st + (addr ^ 64u)));
+            }
         }
     };
     auto mma_half = [&](const AFrags& fa, const BPair& fb, int half) {
@@ -194,7 +246,8 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
         for (int a2 = 0; a2 < 2; ++a2)
 #pragma unroll
             for (int fn = 0; fn < 2; ++fn)
-                acc[a2][2 * half + fn] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(fa.a[a2].v, fb.b[fn].v, acc[a2][2 * half + fn], fa.idx[a2], 0, 0);
+                if (FP8) acc[a2][2 * half + fn] = __builtin_amdgcn_smfmac_f32_32x32x64_fp8_fp8(fa.a[a2].q, fb.b[fn].v8, acc[a2][2 * half + fn], fa.idx[a2], 0, 0);
+                else     acc[a2][2 * half + fn] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(fa.a[a2].v, fb.b[fn].v, acc[a2][2 * half + fn], fa.idx[a2], 0, 0);
     };
 #define SB() __builtin_amdgcn_sched_barrier(0)
 
@@ -250,7 +303,7 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = 8 * (r >> 2) + 4 * lh + (r & 3);
-                    *reinterpret_cast<uint16_t*>(scratch + row * EP + (b * 32 + l32) * 2) = (uint16_t)f2bf(acc[a][2 * half + b][r]);
+                    *reinterpret_cast<uint16_t*>(scratch + row * EP + (b * 32 + l32) * 2) = (uint16_t)f2bf(FP8 ? acc[a][2 * half + b][r] * alpha : acc[a][2 * half + b][r]);
                 }
             wave_lds_sync();
 #pragma unroll
@@ -266,10 +319,13 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
 bool vnm8_gemm_ok(int64_t T, int64_t N, int64_t F, int64_t ldw) {
     return T > 0 && T % 64 == 0 && N > 0 && N % 64 == 0 && F > 0 && F % 64 == 0 && ldw >= N && ldw % 8 == 0 && F * ldw * 2 < ((int64_t)1 << 32);
 }
+bool vnm8_gemm_fp8_ok(int64_t T, int64_t N, int64_t F, int64_t ldw) {
+    return T > 0 && T % 64 == 0 && N > 0 && N % 64 == 0 && F > 0 && F % 128 == 0 && ldw >= N && ldw % 16 == 0 && F * ldw < ((int64_t)1 << 32);
+}
 
-hipError_t launch_vnm8_gemm(const uint16_t* vcb, const uint8_t* mcb, const uint8_t* cixt, const uint16_t* Wk, int64_t ldw, int64_t T, int64_t N,
-                            int64_t F, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp) {
-    if (!vnm8_gemm_ok(T, N, F, ldw)) return hipErrorInvalidValue;
+template <bool FP8>
+static hipError_t launch_impl(const uint16_t* vcb, const uint8_t* mcb, const uint8_t* cixt, const uint8_t* Wk, int64_t ldw, float alpha, int64_t T,
+                              int64_t N, int64_t F, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp) {
     const GemmGroup g = grp ? *grp : GemmGroup();
     if (g.n && (g.role != 0 || g.seg_dev || g.n > GemmGroup::kMaxExperts)) return hipErrorInvalidValue;
     const int tiles_m = (int)((T + 255) / 256), tiles_n = (int)((N + 255) / 256);
@@ -279,9 +335,21 @@ hipError_t launch_vnm8_gemm(const uint16_t* vcb, const uint8_t* mcb, const uint8
         for (int e = 0; e < g.n; ++e) tiles += (g.seg[e + 1] - g.seg[e] + 255) / 256 * tiles_n;
     }
     if (tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL(vnm8_gemm_kernel, dim3((unsigned)tiles), dim3(512), 0, s, vcb, mcb, cixt, Wk, (int)ldw, (int)T, (int)N, (int)F, (int)T, out, ldo,
-                       tiles_m, tiles_n, g);
+    hipLaunchKernelGGL((vnm8_gemm_kernel<FP8>), dim3((unsigned)tiles), dim3(512), 0, s, vcb, mcb, cixt, Wk, (int)ldw, (int)T, (int)N, (int)F, (int)T, out,
+                       ldo, tiles_m, tiles_n, g, alpha);
     return hipGetLastError();
+}
+
+hipError_t launch_vnm8_gemm(const uint16_t* vcb, const uint8_t* mcb, const uint8_t* cixt, const uint16_t* Wk, int64_t ldw, int64_t T, int64_t N,
+                            int64_t F, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp) {
+    if (!vnm8_gemm_ok(T, N, F, ldw)) return hipErrorInvalidValue;
+    return launch_impl<false>(vcb, mcb, cixt, reinterpret_cast<const uint8_t*>(Wk), ldw, 1.0f, T, N, F, out, ldo, s, grp);
+}
+
+hipError_t launch_vnm8_gemm_fp8(const uint8_t* vcb, const uint8_t* mcb, const uint8_t* cixt, const uint8_t* Wq, int64_t ldw, float alpha, int64_t T,
+                                int64_t N, int64_t F, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp) {
+    if (!vnm8_gemm_fp8_ok(T, N, F, ldw)) return hipErrorInvalidValue;
+    return launch_impl<true>(reinterpret_cast<const uint16_t*>(vcb), mcb, cixt, Wq, ldw, alpha, T, N, F, out, ldo, s, grp);
 }
 
 }  // namespace sffn

@@ -36,14 +36,13 @@ struct VnmEpilogue {
     const int32_t* perm = nullptr;
     int logM = 3;
     // fp8 operands (launch_gemm_fp8_blocked, modes 1 / 2): the survivors leave as E4M3 codes quantised with 1 / scale = inv_out: mode 1 writes
-    // vals as codes [T, F / 4] and v24 / m24 as a 2:4 code matrix (v24: pairs of codes in the blocked layout, m24: fp8 metadata units);
-    // mode 2 keeps vals = dy1 in bf16 and writes v24 as codes.  ykept, at, kmask, colidx, meta stay as in the bf16 modes.
+    // vals as codes [T, F / 4], mode 2 keeps vals = dy1 in bf16; both write the codes into vcb.  ykept, at, kmask, colidx, meta stay as in the bf16 modes.
     // fp8 modes 5 / 6: vals = the survivors' codes [T, 2 F / M] in both directions (the operand of the gathered-row kernel); the rest as above.
     float inv_out = 1.0f;
     int at_fp8 = 0;                 // fp8 modes 1 / 2: `at` receives codes (pairs in the blocked layout, [F / 2, T]) instead of bf16
     float* amax = nullptr;          // fp8 modes 1 / 2: amax slots for the survivors' magnitudes (y2 / dy1)
-    // modes 1 / 2, bf16: the operands of the V:2:8 activation GEMM (gemm_vnm8.hip; layouts: vcb_off, mcb_off, cixt_off in common.hpp):
-    // vcb = the survivors (both modes), mcb = their metadata and cixt = the regrouped kept-column offsets (mode 1; mode 2 reuses them)
+    // modes 1 / 2: the operands of the V:2:8 activation GEMM (gemm_vnm8.hip; layouts: vcb_off, mcb_off, cixt_off in common.hpp, fp8: vcb8_off, ...):
+    // vcb = the survivors (both modes; fp8: their codes), mcb = their metadata and cixt = the regrouped kept-column offsets (mode 1; mode 2 reuses them)
     uint16_t* vcb = nullptr;
     uint8_t* mcb = nullptr;
     uint8_t* cixt = nullptr;
@@ -106,6 +105,10 @@ hipError_t launch_vnm_spmm_gather(const uint16_t* a_vals, const uint8_t* a_meta,
 bool vnm8_gemm_ok(int64_t T, int64_t N, int64_t F, int64_t ldw);
 hipError_t launch_vnm8_gemm(const uint16_t* vcb, const uint8_t* mcb, const uint8_t* cixt, const uint16_t* Wk, int64_t ldw, int64_t T, int64_t N,
                             int64_t F, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
+// (fp8 step: codes; F a multiple of 128, Wq = [F, ldw bytes], out = bf16(alpha * sum); the arrays in the layouts of vcb8_off, mcb8_off, cixt8_off)
+bool vnm8_gemm_fp8_ok(int64_t T, int64_t N, int64_t F, int64_t ldw);
+hipError_t launch_vnm8_gemm_fp8(const uint8_t* vcb, const uint8_t* mcb, const uint8_t* cixt, const uint8_t* Wq, int64_t ldw, float alpha, int64_t T,
+                                int64_t N, int64_t F, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 // The same on E4M3 codes: a_codes [T, 2 F / M] + the same metadata and column offsets, Wq = codes [F, ldw bytes], out = bf16(alpha * sum);
 // 4 F / M a multiple of 128; b_stride of grp in bytes.
 bool vnm_spmm_gather_fp8_ok(int64_t T, int64_t N, int64_t F, int M);
@@ -176,28 +179,24 @@ hipError_t launch_spmm24_fp8(const uint8_t* a_codes, const uint8_t* a_meta, cons
                              int64_t K, int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s);
 
 // The same contraction on operands in the blocked layout with a pair of codes per 2-byte element (the fused fp8 step): a_codes = packed 2:4
-// codes [Ra, K/2], a_meta in the fp8 metadata units of common.hpp, Bq = codes [Rb, K].  ep = nullptr: out[i * ldo + j] (eqs. (3), (7): Ra = tokens);
-// ep (mode 1 or 2: M = 8; mode 5 or 6: M = 2^logM = 16, 32, 64): eq. (1) / eq. (4) with the fused V:N:M epilogue, Ra = hidden units, Rb = tokens,
-// out [T, F] if ep->store_dense.
+// codes [Ra, K/2], a_meta in the fp8 metadata units of common.hpp, Bq = codes [Rb, K]; eq. (1) / eq. (4) with the fused V:N:M epilogue ep
+// (mode 1 or 2: M = 8; mode 5 or 6: M = 2^logM = 16, 32, 64), Ra = hidden units, Rb = tokens, out [T, F] if ep->store_dense.
 hipError_t launch_gemm_fp8_blocked(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* Bq, const float* bias, float alpha, int64_t Ra,
                                    int64_t Rb, int64_t K, uint16_t* out, int64_t ldo, const VnmEpilogue* ep, hipStream_t s, const GemmGroup* grp = nullptr);
 // fp8.hip, producers of such operands: quantised copy in the same orientation / transposed; 2:4 pruning that also writes the blocked codes
 // (amax, optional: the tensor's amax slots, see below)
 hipError_t launch_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_blk, hipStream_t s, float* amax = nullptr);
-// (out_same_blk: also the codes in the source's orientation; p_codes / p_meta / p_blk: also the 2:4 pruning of the rows, mode prune_mode, canonical
-//  codes [R, C/2] + metadata [R, C/8] + blocked codes + metadata units (p_mblk); at most one of the two extras)
+// (out_same_blk: also the codes in the source's orientation)
 hipError_t launch_transpose_quantize_fp8_blocked(const uint16_t* src, int64_t R, int64_t C, int64_t ld, float inv, uint8_t* out_t_blk, hipStream_t s,
-                                                 float* amax = nullptr, uint8_t* out_same_blk = nullptr, int prune_mode = 0, uint8_t* p_codes = nullptr,
-                                                 uint8_t* p_meta = nullptr, uint8_t* p_blk = nullptr, uint8_t* p_mblk = nullptr);
+                                                 float* amax = nullptr, uint8_t* out_same_blk = nullptr);
 // amax slots of the fused fp8 step: n tensors x 64 slots x 256 bytes (kAmaxSlots, kAmaxSlotStride in common.hpp); the step's kernels take a tensor's slot base
 hipError_t launch_amax_clear(float* slots, int n, hipStream_t s);
 hipError_t launch_amax_finish(const float* slots, int n, float* out, hipStream_t s);
-// (meta_blk: the metadata in the fp8 units of common.hpp; src_q_blk, trans = 1 only: also the unpruned source quantised in its own orientation,
-//  [K rows, R codes], blocked; s_q: also the unpruned logical matrix [R, K] quantised, row-major codes (the gathered operand of eqs. (3), (7)
-//  for M >= 16); amax_src: amax slots of the unpruned tensor; codes / meta may be null)
+// 2:4 pruning + quantisation for the fp8 step, rows (trans = 0) or strided groups (trans = 1): the packed codes blocked (codes_blk) with the metadata in
+// the fp8 units of common.hpp (meta_blk), and s_q = the unpruned logical matrix [R, K] itself as row-major codes (the operand of eqs. (3), (7),
+// whose kept rows are picked or gathered per token block); amax_src: amax slots of the unpruned tensor; codes / meta (canonical) may be null
 hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float inv, uint8_t* codes, uint8_t* meta,
-                                   uint8_t* codes_blk, uint8_t* meta_blk, hipStream_t s, uint8_t* src_q_blk = nullptr, float* amax_src = nullptr,
-                                   uint8_t* s_q = nullptr);
+                                   uint8_t* codes_blk, uint8_t* meta_blk, hipStream_t s, float* amax_src, uint8_t* s_q);
 
 // the same on E4M3 codes (atc: compact transposed codes [F / 2, T], Gq [N, T], both in the blocked pair layout): out = bf16(alpha * sum)
 hipError_t launch_wgrad_vnm_fp8(const uint8_t* atc, const uint8_t* kmask, const uint8_t* Gq, float alpha, int64_t F, int64_t N, int64_t T,
