@@ -231,6 +231,20 @@ int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_col
     uint8_t* m24 = ws + up256((size_t)T * Kfull);
     const uint16_t* W = Wd;
     uint16_t* wcopy = (uint16_t*)(m24 + up256((size_t)T * Kfull / 8));
+    if (M == 8 && vnm8_gemm_ok(T, N, Kfull, w_kmajor ? ldw : N)) {
+        // the 256-token tile kernel of the fused step: the packed arrays regrouped into its units (one small pass), Wd contraction-major
+        uint16_t* vcb = v24;
+        uint8_t* mcb = m24;
+        uint8_t* cixt = m24 + up256((size_t)T * Kfull / 16);
+        int64_t ldk = ldw;
+        if (!w_kmajor) {
+            LAUNCH(launch_transpose(Wd, N, Kfull, ldw, wcopy, 0, nullptr, s), "vnm_spmm/transpose");
+            W = wcopy; ldk = N;
+        }
+        LAUNCH(launch_vnm8_repack(a_vals, a_meta, a_colidx, T, Kfull, vcb, mcb, cixt, s), "vnm_spmm/repack");
+        LAUNCH(launch_vnm8_gemm(vcb, mcb, cixt, W, ldk, T, N, Kfull, out, N, s), "vnm_spmm/gemm");
+        return SFFN_OK;
+    }
     if ((M >= 16 || w_kmajor) && vnm_spmm_gather_ok(T, N, Kfull, M) && Kfull * (w_kmajor ? ldw : N) * 2 < ((int64_t)1 << 32)) {
         // contract over the 4 Kfull / M kept columns only, gathering their rows of the [Kfull, N] operand (M = 8: the two routes
         // are equally fast, so it is taken only when it saves the transpose of Wd)

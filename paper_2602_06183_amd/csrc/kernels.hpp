@@ -105,6 +105,9 @@ hipError_t launch_vnm_spmm_gather(const uint16_t* a_vals, const uint8_t* a_meta,
 bool vnm8_gemm_ok(int64_t T, int64_t N, int64_t F, int64_t ldw);
 hipError_t launch_vnm8_gemm(const uint16_t* vcb, const uint8_t* mcb, const uint8_t* cixt, const uint16_t* Wk, int64_t ldw, int64_t T, int64_t N,
                             int64_t F, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
+// vnm.hip: the canonical V:2:8 arrays (vals [T, F/4], meta [T, F/16], colidx [T/64, F/8, 4]) regrouped into those units
+hipError_t launch_vnm8_repack(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F, uint16_t* vcb, uint8_t* mcb,
+                              uint8_t* cixt, hipStream_t s);
 // (fp8 step: codes; F a multiple of 128, Wq = [F, ldw bytes], out = bf16(alpha * sum); the arrays in the layouts of vcb8_off, mcb8_off, cixt8_off)
 bool vnm8_gemm_fp8_ok(int64_t T, int64_t N, int64_t F, int64_t ldw);
 hipError_t launch_vnm8_gemm_fp8(const uint8_t* vcb, const uint8_t* mcb, const uint8_t* cixt, const uint8_t* Wq, int64_t ldw, float alpha, int64_t T,

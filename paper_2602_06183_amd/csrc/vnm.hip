@@ -145,6 +145,40 @@ hipError_t launch_dsqrelu_vnm(const uint16_t* dy2, const uint16_t* y1, const uin
     return hipGetLastError();
 }
 
+// The canonical V:2:8 arrays regrouped into the units of the V:2:8 activation GEMM (gemm_vnm8.hip; the fused epilogues write them directly):
+// one thread per (token, 64 hidden units) moves 16 survivors and 4 metadata bytes; the first 8 threads of a token block also build the 8
+// offset words of their (token block, 64 hidden units).
+__global__ void __launch_bounds__(256) vnm8_repack_kernel(const uint16_t* __restrict__ vals, const uint8_t* __restrict__ meta,
+                                                         const uint8_t* __restrict__ colidx, int64_t T, int F, uint16_t* __restrict__ vcb,
+                                                         uint8_t* __restrict__ mcb, uint8_t* __restrict__ cixt) {
+    const int KS = F >> 6;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= T * KS) return;
+    const int64_t t = i / KS;
+    const int kt = (int)(i - t * KS);
+    const uint4* src = reinterpret_cast<const uint4*>(vals + t * (F >> 2) + kt * 16);
+    uint4* dst = reinterpret_cast<uint4*>(vcb + vcb_off(t, (int64_t)kt * 8, F));
+    dst[0] = src[0];
+    dst[1] = src[1];
+    *reinterpret_cast<uint32_t*>(mcb + mcb_off(t, kt, F)) = *reinterpret_cast<const uint32_t*>(meta + t * (F >> 4) + kt * 4);
+    const int q = (int)(t & 63);
+    if (q < 8) {        // word (h, r), byte j = kept column r of column block 4 (j / 2) + j % 2 + 2 h
+        const int h = q >> 2, r = q & 3;
+        const uint8_t* c = colidx + ((t >> 6) * (F >> 3) + kt * 8) * 4;
+        uint32_t dw = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dw |= (uint32_t)c[(4 * (j >> 1) + (j & 1) + 2 * h) * 4 + r] << (8 * j);
+        *reinterpret_cast<uint32_t*>(cixt + cixt_off(t >> 6, kt, T >> 6) + q * 4) = dw;
+    }
+}
+
+hipError_t launch_vnm8_repack(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F, uint16_t* vcb, uint8_t* mcb,
+                              uint8_t* cixt, hipStream_t s) {
+    const int64_t n = T * (F / 64);
+    hipLaunchKernelGGL(vnm8_repack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, vals, meta, colidx, T, (int)F, vcb, mcb, cixt);
+    return hipGetLastError();
+}
+
 hipError_t launch_vnm_to_24(const uint16_t* vals, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F,
                             uint16_t* vals24, uint8_t* meta24, hipStream_t s) {
     const int nblk = (int)(F / 8);
