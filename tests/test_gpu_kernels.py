@@ -420,6 +420,25 @@ def test_vnm_spmm_gathered_rows(M, T, F, N):
     assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.vnm_spmm(iv, im, ic, Wi, 1, 64, M)))
 
 
+@pytest.mark.parametrize("T,F,N,pad", [(64, 64, 64, 0), (320, 192, 576, 0), (576, 256, 320, 64), (256, 128, 64, 8), (832, 448, 256, 0)])
+def test_vnm_spmm_m8_tile_kernel_edges(T, F, N, pad):
+    """The V:2:8 activation kernel (256-token tiles, kept rows picked at the fragment reads) through vnm_spmm: partial token and column
+    tiles, fewer stages than its ring holds (F = 64, 128), a padded row stride of the dense matrix, both orientations; small integers, so
+    every product and sum is exact and the result must equal the oracle's bit for bit."""
+    rng = np.random.default_rng(T + F + N)
+    yi = bf16_bits_from_f32(rng.integers(-3, 4, size=(T, F)).astype(np.float32))
+    iv, im, ic = oracle.sqrelu_vnm_compress(yi, 64, 8)
+    div, dim, dic = to_dev(iv), to_dev(im), to_dev(ic)
+    Wk = bf16_bits_from_f32(rng.integers(-2, 3, size=(F, N + pad)).astype(np.float32))            # [Kfull, N (+ padding)]
+    got = to_bits(sffn.vnm_spmm(div, dim, dic, to_dev(Wk)[:, :N], 1))
+    want = oracle.vnm_spmm(iv, im, ic, np.ascontiguousarray(Wk[:, :N]), 1)
+    assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(want))
+    assert np.count_nonzero(oracle.bits_to_f32(want)) > want.size // 4
+    Wn = np.ascontiguousarray(Wk[:, :N].T)                                                        # [N, Kfull]
+    got = to_bits(sffn.vnm_spmm(div, dim, dic, to_dev(Wn), 0))
+    assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(want))
+
+
 @pytest.mark.parametrize("M,mode,F", [(16, sffn.MODE_HARD, 640), (32, sffn.MODE_SOFT, 640), (64, sffn.MODE_HARD, 640),
                                       (16, sffn.MODE_SOFT, 1024), (32, sffn.MODE_HARD, 1024), (64, sffn.MODE_SOFT, 1024)])
 def test_ffn_sparse_step_wide_blocks(M, mode, F):
