@@ -873,9 +873,9 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
             SFFN_EINVAL, "ffn_sparse_step: pointers must be 16-byte aligned");
     REQUIRE(cfg->T < 65536 && fits_int(cfg->F * n_experts) && fits_int(cfg->D), SFFN_EUNSUPPORTED,
             "ffn_sparse_step: T must be below 65536 and F * n_experts below 2^31");
-    REQUIRE(workspace && ws_bytes >= L.total, SFFN_EWORKSPACE, "ffn_sparse_step: workspace missing or too small");
     const int64_t T = cfg->T, D = cfg->D, F = cfg->F, E = n_experts;
     REQUIRE(cfg->M != 8 || F * D * 2 < ((int64_t)1 << 32), SFFN_EUNSUPPORTED, "ffn_sparse_step: a weight matrix must stay below 4 GiB");
+    REQUIRE(workspace && ws_bytes >= L.total, SFFN_EWORKSPACE, "ffn_sparse_step: workspace missing or too small");
     GemmGroup g;                                    // g.n = 0: plain step
     if (seg) {
         REQUIRE(seg[0] == 0 && seg[E] == T, SFFN_EINVAL, "ffn_sparse_step_grouped: seg_offsets must start at 0 and end at T");

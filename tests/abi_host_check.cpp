@@ -25,7 +25,7 @@ int main() {
     EXPECT(spmm24_fwd(fake, fake, fake8, nullptr, 64, 64, 65, fake, nullptr), SFFN_EINVAL);
     EXPECT(spmm24_dgrad(fake, fake, nullptr, 64, 64, 64, fake, nullptr), SFFN_EINVAL);
     EXPECT(vnm_spmm(fake, fake8, fake8, fake, 64, 0, 64, 64, 64, 64, 8, fake, nullptr, 0, nullptr), SFFN_EWORKSPACE);
-    EXPECT(vnm_spmm(fake, fake8, fake8, fake, 192, 0, (int64_t)1 << 20, 64, 192, 64, 8, fake, ws, (size_t)1 << 40, nullptr), SFFN_EUNSUPPORTED);   // plain-2:4 route: T below 65536
+    EXPECT(vnm_spmm(fake, fake8, fake8, fake, 192, 0, (int64_t)1 << 20, 64, 192, 64, 16, fake, ws, (size_t)1 << 40, nullptr), SFFN_EUNSUPPORTED);   // plain-2:4 route (4 * 192 / 16 is not a multiple of 64): T below 65536
     EXPECT(dsqrelu_vnm(fake, fake, fake8, fake8, 64, 100, 64, 8, fake, nullptr), SFFN_EINVAL);
     EXPECT(vnm_wgrad(fake, fake8, fake8, fake, 64, 64, 64, 64, 8, 0, fake, ws, 16, nullptr), SFFN_EWORKSPACE);
     EXPECT(quantize_fp8(fake, 12, 1.0f, fake8, nullptr, nullptr), SFFN_EINVAL);

@@ -69,6 +69,8 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     bad = binding._Cfg(512, 250, 1024, 64, 8, 0, 0)
     assert lib.ffn_sparse_step(ctypes.byref(bad), *args, fake, 1 << 30, None) == -1
     assert len(lib.sffn_last_error()) > 0
+    huge = binding._Cfg(64, 32768, 65536, 64, 8, 0, 0)                    # a 4 GiB weight matrix: beyond the 32-bit offsets of the V:2:8 kernel's loads
+    assert lib.ffn_sparse_step(ctypes.byref(huge), *args, fake, 1 << 50, None) == -2
     # the fp8 step: scales are a host struct; shapes, flags, scales and the workspace are checked before anything is enqueued
     sc = binding._Fp8Scales(1.0, 1.0, 1.0, 1.0, 1.0, 1.0)
     assert lib.ffn_sparse_step_fp8(ctypes.byref(cfg), None, *args, fake, 1 << 40, None, None) == -1                 # no scales
