@@ -141,12 +141,12 @@ int spmm24_prepared(const uint16_t* X, const void* w_prepared, const float* bias
  * (w_kmajor=1, Wd = W1 [Kfull,N]): out[t,n] = bf16( sum_f Av[t,f] * W(n,f) ) with Av the V:N:M
  * matrix (a_vals [T,Kfull/4], a_meta [T,Kfull/16], a_colidx [T/64,Kfull/8,4]) and W dense.
  * ldw = row stride of Wd in elements.  workspace: sffn_vnm_spmm_workspace_bytes() (the same size
- * for both orientations: scratch for the activation re-expressed as plain 2:4 and for a transposed
- * copy of Wd).  Route: when 4*Kfull/M is a multiple of 64 and at most 7168 (and M >= 16, or M = 8
- * with w_kmajor=1) only the kept rows of the contraction-major W take part (gathered per 64-token
- * block); otherwise the activation is contracted as a plain 2:4 matrix over all Kfull columns.
- * Both routes compute the same sums (fp32 accumulation order differs).  T is below 2^22 on the gathered route and
- * below 65536 on the plain-2:4 route (SFFN_EUNSUPPORTED beyond, nothing enqueued). */
+ * for both orientations: scratch for the activation in the layout the kernel of the route reads and for a
+ * transposed copy of Wd).  Routes: M = 8 (Wd below 4 GiB): the packed activation as it is on 256-token tiles, the
+ * kept rows of the contraction-major W picked while the fragments are read; M >= 16 with 4*Kfull/M a multiple of 64
+ * and at most 7168: only the kept rows of W are fetched (gathered per 64-token block); otherwise the activation
+ * is contracted as a plain 2:4 matrix over all Kfull columns.  All routes compute the same sums (fp32 accumulation
+ * order differs).  T is below 2^22, and below 65536 on the plain-2:4 route (SFFN_EUNSUPPORTED beyond, nothing enqueued). */
 int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_colidx,
              const uint16_t* Wd, int64_t ldw, int w_kmajor, int64_t T, int64_t N, int64_t Kfull,
              int V, int M, uint16_t* out, void* workspace, size_t ws_bytes, void* stream);
