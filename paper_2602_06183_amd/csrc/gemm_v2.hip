@@ -346,23 +346,42 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         const int nblk = Ra >> 3;
         const int64_t F = Ra;
         uint32_t nib_h0 = 0;                                  // M = 64: the metadata nibble of the first half waits for the second's
+        // The lane's 32 bias values of each half, and (EPI 2) the saved column offsets, metadata and y1 of its 8 sweeps: all fetched here, for
+        // both halves.  Loads and stores share one in-order counter, so a load issued after the first half's stores would wait for all of them
+        // (and for its own latency) in the middle of the epilogue.
+        float4 bb_all[2][2][4];
+        uint32_t pre_cw[2] = {0x03020100u, 0x03020100u}, pre_m_all[2][8], pre_y_all[2][8];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int f0 = i0 + wm * WM + h * 64;
-            const bool valid = t0 < Rb && f0 < Ra;
-            // the lane's 32 bias values of this half, fetched together (one wait instead of one per store)
-            float4 bb[2][4];
 #pragma unroll
             for (int a2 = 0; a2 < 2; ++a2)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    bb[a2][g] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    bb_all[h][a2][g] = make_float4(0.f, 0.f, 0.f, 0.f);
                     if (bias) {
                         int i = f0 + a2 * 32 + 8 * g + 4 * lh; i = i < Ra ? i : Ra - 4;
                         // EPI 3: compact column i of the expert is hidden unit (i / 4) * M + 4 e + i % 4 (bias already points at 4 e)
-                        bb[a2][g] = *reinterpret_cast<const float4*>(EPI == 3 ? bias + ((int64_t)(i >> 2) << ep.logM) : bias + i);
+                        bb_all[h][a2][g] = *reinterpret_cast<const float4*>(EPI == 3 ? bias + ((int64_t)(i >> 2) << ep.logM) : bias + i);
                     }
                 }
+            if (EPI == 2 && t0 < Rb && f0 < Ra) {
+                const int64_t blk = (f0 >> 3) + (lane & 7);
+                pre_cw[h] = *reinterpret_cast<const uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblk + blk) * 4);
+                const uint32_t* kp = reinterpret_cast<const uint32_t*>(ep.ykept) + ykept_off(t0 + (lane >> 3), blk, F);
+                const uint8_t* mp = ep.meta + (int64_t)(t0 + (lane >> 3)) * (F / 16) + (blk >> 1);
+#pragma unroll
+                for (int it = 0; it < 8; ++it) {
+                    pre_m_all[h][it] = mp[(int64_t)it * 8 * (F / 16)];
+                    pre_y_all[h][it] = kp[it * 64];
+                }
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int f0 = i0 + wm * WM + h * 64;
+            const bool valid = t0 < Rb && f0 < Ra;
+            float4 (&bb)[2][4] = bb_all[h];
             bool tok_ok[FN];                                   // EPI 3: padding rows of the permuted token order come out as zeros
 #pragma unroll
             for (int b = 0; b < FN; ++b) {
@@ -632,7 +651,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         if (valid && lane < 8) *reinterpret_cast<uint32_t*>(ep.cixt + cixt_off(t0 >> 6, f0 >> 6, tok_ld >> 6) + q * 4) = dw;
                     }
                 } else {
-                    cw = valid ? *reinterpret_cast<const uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblk + blk_g) * 4) : 0x03020100u;
+                    cw = pre_cw[h];
                 }
                 // per-row pass: lane = (column block bl, token t); 8 tokens per sweep, 8 sweeps
                 uint32_t* vals_p = reinterpret_cast<uint32_t*>(ep.vals) + ((int64_t)(t0 + (lane >> 3)) * (F / 4) + blk_g * 2) / 2;
@@ -643,14 +662,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                 uint8_t* vcb8_p = FP8 ? reinterpret_cast<uint8_t*>(ep.vcb) + vcb8_off(t0 + (lane >> 3), blk_g, F) : nullptr;   // (the lane of block 0 stores its row's 8 pairs of codes)
                 uint8_t* mcb_p = FP8 ? ep.mcb + mcb8_off(t0 + (lane >> 3), f0 >> 6, F) : ep.mcb + mcb_off(t0 + (lane >> 3), f0 >> 6, F);
                 const uint32_t c0 = (cw & 0xFFu) * 2, c1 = ((cw >> 8) & 0xFFu) * 2, c2 = ((cw >> 16) & 0xFFu) * 2, c3 = (cw >> 24) * 2;
-                uint32_t pre_m[8], pre_y[8];                                // EPI 2: saved metadata and y1 of the 8 sweeps, fetched together
-                if (EPI == 2 && valid) {
-#pragma unroll
-                    for (int it = 0; it < 8; ++it) {
-                        pre_m[it] = meta_p[(int64_t)it * 8 * (F / 16)];
-                        pre_y[it] = kept_p[it * 64];
-                    }
-                }
+                const uint32_t (&pre_m)[8] = pre_m_all[h];                  // EPI 2: saved metadata and y1 of the 8 sweeps
+                const uint32_t (&pre_y)[8] = pre_y_all[h];
                 float vmax = 0.0f;                                         // fp8: largest survivor magnitude of this half tile
                 if (valid) {
 #pragma unroll
