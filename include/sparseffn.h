@@ -70,10 +70,10 @@ typedef struct sffn_cfg {
  * (4 F / M not a multiple of 64 or above 7168) take it in any case. */
 #define SFFN_FLAG_UNFUSED 2
 #define SFFN_FLAG_FP8_WGRAD 4     /* ffn_sparse_step_fp8 only: eqs. (5), (8) on codes as well */
-/* ffn_sparse_step / ffn_sparse_step_grouped with M = 8: do not write the canonical copies w1_vals / w1_meta, w2t_vals / w2t_meta,
- * y2_vals and (when eq. (7) does not read it) dy1_vals of sffn_ws_layout.  They are inspection aids: every consumer inside the step
- * reads its own operand layouts, and Y3, dX, dW1, dW2, y2_meta, colidx, y1_kept are the same bits with or without the flag.  Ignored
- * for M > 8. */
+/* ffn_sparse_step / ffn_sparse_step_grouped: do not write the canonical copies w1_vals / w1_meta, w2t_vals / w2t_meta and, at M = 8,
+ * y2_vals and dy1_vals of sffn_ws_layout (at M >= 16 eqs. (3), (7) read those two).  They are inspection aids: every consumer inside the
+ * step reads its own operand layouts, and Y3, dX, dW1, dW2, y2_meta, colidx, y1_kept are the same bits with or without the flag.  Ignored
+ * by the unfused path. */
 #define SFFN_FLAG_LEAN 8
 
 /* Byte offsets, inside the workspace of ffn_sparse_step, of the tensors Alg. 2 line 1 saves

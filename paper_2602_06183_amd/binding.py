@@ -352,8 +352,9 @@ class FfnStep:
     def __init__(self, T, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8, unfused=False, lean=False):
         """keep_dense: also store the dense y1 and dy2 (SFFN_FLAG_KEEP_DENSE); otherwise only y1 at y2's kept
         slots is saved for the backward pass.  M: V:N:M block width, 8, 16, 32 or 64.  unfused (M >= 16): the path
-        with separate eq. (2) / eq. (6) kernels that always stores y1 and dy2 and produces no y1_kept.  lean (M = 8):
-        the canonical copies of the packed tensors are not written (SFFN_FLAG_LEAN); saved() then holds stale data for them."""
+        with separate eq. (2) / eq. (6) kernels that always stores y1 and dy2 and produces no y1_kept.  lean:
+        the canonical copies of the packed weights (and, at M = 8, of the packed activations) are not written (SFFN_FLAG_LEAN);
+        saved() then holds stale data for them."""
         self.T, self.D, self.F, self.mode, self.keep_dense, self.M = T, D, F, mode, keep_dense, M
         self.cfg = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused, lean))
         self.layout = workspace_layout(T, D, F, mode, M, keep_dense, unfused)

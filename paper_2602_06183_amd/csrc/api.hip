@@ -920,13 +920,14 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
         uint16_t* w2t = w1tb;                            // W2.T [F, D] per expert
         if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
         STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
-        STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, w1v, w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
+        const bool lean_w = (cfg->flags & SFFN_FLAG_LEAN) != 0;        // no canonical copies of the packed weights (the packed activations stay: eqs. (3), (7) read them)
+        STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, lean_w ? nullptr : w1v, lean_w ? nullptr : w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
         {
             VnmEpilogue ep;
             ep.mode = 5; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = y2v; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept; ep.at = atb;
             STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s, gp), "step/y1+sqrelu_vnm_compress");         // eqs. (1), (2), Section 2.3
         }
-        STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, w2v, w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
+        STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, lean_w ? nullptr : w2v, lean_w ? nullptr : w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
         STAGE(launch_vnm_spmm_gather(y2v, y2m, cix, w2t, D, T, D, F, M, Y3, D, s, gr), "step/y3");                              // eq. (3)
         STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
         STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");                                       // eq. (5)

@@ -136,6 +136,20 @@ __host__ __device__ __forceinline__ int64_t cixt8_off(int64_t tb, int64_t s128, 
     return (s128 * n_tok_blocks + tb) << 6;
 }
 
+// The same in two steps, for kernels whose stores would otherwise stand between the early-out read and its use (loads and stores share one
+// in-order counter): amax_slot_peek reads the workgroup's slot before the stores are issued, note_amax_slots_seen compares against that value.
+__device__ __forceinline__ uint32_t amax_slot_peek(const float* slots) {
+    if (!slots) return 0u;
+    const unsigned int* p = reinterpret_cast<const unsigned int*>(slots + (((blockIdx.y * gridDim.x + blockIdx.x) & (kAmaxSlots - 1)) * kAmaxSlotStride));
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void note_amax_slots_seen(float* slots, float m, uint32_t seen) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) m = __builtin_fmaxf(m, __shfl_xor(m, o, 64));
+    if (slots && (threadIdx.x & 63) == 0 && __float_as_uint(m) > seen)
+        atomicMax(reinterpret_cast<unsigned int*>(slots + (((blockIdx.y * gridDim.x + blockIdx.x) & (kAmaxSlots - 1)) * kAmaxSlotStride)), __float_as_uint(m));
+}
+
 // Two survivors per 8 columns leave at most two per aligned group of four, so a V:2:8 row block is
 // also two plain 2:4 groups.  Inputs: v = the two survivors (low half first), nib = their positions
 // among the four kept columns, cw = the four kept column offsets (one per byte).  Outputs: the two

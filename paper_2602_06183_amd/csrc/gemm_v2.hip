@@ -351,6 +351,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         // (and for its own latency) in the middle of the epilogue.
         float4 bb_all[2][2][4];
         uint32_t pre_cw[2] = {0x03020100u, 0x03020100u}, pre_m_all[2][8], pre_y_all[2][8];
+        const uint32_t amax_seen = (FP8 && EPI != 0) ? amax_slot_peek(ep.amax) : 0u;
+        float vmax_tile = 0.0f;                                 // fp8: largest survivor magnitude of the wave's tile
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int f0 = i0 + wm * WM + h * 64;
@@ -377,17 +379,38 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                 }
             }
         }
+        // (the same for the backward epilogue of the wide blocks)
+        constexpr int GNB = (GEN_F || GEN_B) ? (64 >> LOGM) : 1;
+        uint32_t gpre_cb[2] = {0x03020100u, 0x03020100u}, gpre_m[2][GNB], gpre_y[2][GNB];
+        if (GEN_B) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int f0 = i0 + wm * WM + h * 64;
+                if (t0 < Rb && f0 < Ra) {
+                    const int b = lane & (GNB - 1), r_lane = lane >> (6 - LOGM);
+                    const int64_t blk = (f0 >> LOGM) + b;
+                    gpre_cb[h] = *reinterpret_cast<const uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * (F >> LOGM) + blk) * 4);
+                    const uint32_t* kp = reinterpret_cast<const uint32_t*>(ep.ykept) + ((((int64_t)(t0 >> 6) * (F >> 6) + (f0 >> 6)) << 6) + r_lane) * GNB + b;
+                    const uint8_t* mp = ep.meta + (int64_t)(t0 + r_lane) * (F >> (LOGM + 1)) + (blk >> 1);
+#pragma unroll
+                    for (int sw = 0; sw < GNB; ++sw) {
+                        gpre_m[h][sw] = mp[(int64_t)sw * (1 << LOGM) * (F >> (LOGM + 1))];
+                        gpre_y[h][sw] = kp[sw * (1 << LOGM) * GNB];
+                    }
+                }
+            }
+        }
+        bool tok_ok[FN];                                       // EPI 3: padding rows of the permuted token order come out as zeros
+#pragma unroll
+        for (int b = 0; b < FN; ++b) {
+            tok_ok[b] = true;
+            if (EPI == 3) { int j = t0 + b * 32 + l32; j = j < Rb ? j : Rb - 1; tok_ok[b] = ep.perm[j] >= 0; }
+        }
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int f0 = i0 + wm * WM + h * 64;
             const bool valid = t0 < Rb && f0 < Ra;
             float4 (&bb)[2][4] = bb_all[h];
-            bool tok_ok[FN];                                   // EPI 3: padding rows of the permuted token order come out as zeros
-#pragma unroll
-            for (int b = 0; b < FN; ++b) {
-                tok_ok[b] = true;
-                if (EPI == 3) { int j = t0 + b * 32 + l32; j = j < Rb ? j : Rb - 1; tok_ok[b] = ep.perm[j] >= 0; }
-            }
 #pragma unroll
             for (int a2 = 0; a2 < 2; ++a2)
 #pragma unroll
@@ -520,7 +543,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                     bmask = (unsigned long long)(uint32_t)__shfl((int)(uint32_t)mine, b << LOGM, 64);
                     if (M == 64) bmask |= (unsigned long long)(uint32_t)__shfl((int)(uint32_t)(mine >> 32), b << LOGM, 64) << 32;
                 } else {
-                    cb = valid ? *reinterpret_cast<const uint32_t*>(ep.colidx + ((int64_t)(t0 >> 6) * nblkM + blk0 + b) * 4) : 0x03020100u;
+                    cb = gpre_cb[h];
                     bmask = (1ull << (cb & 0xFFu)) | (1ull << ((cb >> 8) & 0xFFu)) | (1ull << ((cb >> 16) & 0xFFu)) | (1ull << (cb >> 24));
                 }
                 const uint32_t q0 = (cb & 0xFFu) * 2, q1 = ((cb >> 8) & 0xFFu) * 2, q2 = ((cb >> 16) & 0xFFu) * 2, q3 = (cb >> 24) * 2;
@@ -531,14 +554,8 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                 float vmax = 0.0f;                                        // fp8: largest survivor magnitude of this half tile
                 uint32_t* kept_p = reinterpret_cast<uint32_t*>(ep.ykept) + ((((int64_t)(t0 >> 6) * (F >> 6) + (f0 >> 6)) << 6) + r_lane) * NB + b;
                 uint8_t* meta_p = ep.meta + (int64_t)(t0 + r_lane) * (F >> (LOGM + 1)) + ((blk0 + b) >> 1);
-                uint32_t pre_m[NB], pre_y[NB];
-                if (GEN_B && valid) {
-#pragma unroll
-                    for (int sw = 0; sw < NB; ++sw) {
-                        pre_m[sw] = meta_p[(int64_t)sw * M * (F >> (LOGM + 1))];
-                        pre_y[sw] = kept_p[sw * M * NB];
-                    }
-                }
+                const uint32_t (&pre_m)[GNB] = gpre_m[h];                 // backward: saved metadata and y1 of the sweeps (fetched above)
+                const uint32_t (&pre_y)[GNB] = gpre_y[h];
                 if (valid) {
 #pragma unroll
                     for (int sw = 0; sw < NB; ++sw) {
@@ -591,7 +608,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         *reinterpret_cast<uint16_t*>(ttile + r1 * EP + t * 2) = (uint16_t)(v >> 16);
                     }
                 }
-                if (FP8 && ep.amax) note_amax_slots(ep.amax, vmax);
+                if (FP8) vmax_tile = __builtin_fmaxf(vmax_tile, vmax);
                 wave_lds_sync();
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {          // 2 groups of 16 compact rows x 2 chunks of 32 tokens, 1 KB each
@@ -718,7 +735,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                         *reinterpret_cast<uint16_t*>(ttile + (bl * 4 + (nib >> 2)) * EP + t * 2) = (uint16_t)(v >> 16);
                     }
                 }
-                if (FP8 && ep.amax) note_amax_slots(ep.amax, vmax);
+                if (FP8) vmax_tile = __builtin_fmaxf(vmax_tile, vmax);
                 wave_lds_sync();
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {          // 2 groups of 16 compact rows x 2 chunks of 32 tokens, 1 KB each
@@ -736,6 +753,7 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
             }
             wave_lds_sync();
         }
+        if (FP8 && EPI != 0 && ep.amax) note_amax_slots_seen(ep.amax, vmax_tile, amax_seen);
     } else {
         constexpr int EP = WN * 2 + 16;
         unsigned char* scratch = smem + wave * (32 * EP);

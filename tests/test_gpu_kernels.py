@@ -666,8 +666,7 @@ def test_ffn_router_step_with_empty_experts():
 @pytest.mark.parametrize("T,D,F,mode", [(512, 256, 1024, sffn.MODE_HARD), (192, 320, 448, sffn.MODE_SOFT), (128, 128, 14464, sffn.MODE_HARD)])
 def test_lean_step_is_bit_identical(T, D, F, mode):
     """SFFN_FLAG_LEAN leaves out the canonical copies of the packed tensors and nothing else: the four outputs and what the
-    backward pass needs (metadata, column indices, y1 at the kept slots) are the same bits.  (The third shape takes the
-    2:4-view route for eq. (7), where the canonical dy1 is skipped too.)"""
+    backward pass needs (metadata, column indices, y1 at the kept slots) are the same bits."""
     inp = make_ffn_inputs(T, D, F, seed=6)
     dev = {k: to_dev(v) for k, v in inp.items()}
     full, lean = sffn.FfnStep(T, D, F, mode), sffn.FfnStep(T, D, F, mode, lean=True)
@@ -680,6 +679,24 @@ def test_lean_step_is_bit_identical(T, D, F, mode):
     for k in ("y2_meta", "colidx", "y1_kept"):
         assert np.array_equal(to_bits(sa[k]), to_bits(sb[k])), k
     assert np.all(to_bits(sb["w1_vals"]) == 0xA5A5) and np.all(to_bits(sb["y2_vals"]) == 0xA5A5)       # really not written
+
+
+@pytest.mark.parametrize("M", [16, 64])
+def test_lean_wide_block_step_is_bit_identical(M):
+    """The fused wide-block step with SFFN_FLAG_LEAN: the packed weights' canonical copies are not written, everything else is the same bits."""
+    T, D, F = 256, 256, 1024
+    inp = make_ffn_inputs(T, D, F, seed=8)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    full, lean = sffn.FfnStep(T, D, F, sffn.MODE_SOFT, M=M), sffn.FfnStep(T, D, F, sffn.MODE_SOFT, M=M, lean=True)
+    lean.ws.fill_(0xA5)
+    a = [to_bits(t).copy() for t in full(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    b = [to_bits(t).copy() for t in lean(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    for name, x, y in zip(("Y3", "dX", "dW1", "dW2"), a, b):
+        assert np.array_equal(x, y), name
+    sa, sb = full.saved(), lean.saved()
+    for k in ("y2_vals", "y2_meta", "colidx", "dy1_vals", "y1_kept"):
+        assert np.array_equal(to_bits(sa[k]), to_bits(sb[k])), k
+    assert np.all(to_bits(sb["w1_vals"]) == 0xA5A5) and np.all(to_bits(sb["w2t_vals"]) == 0xA5A5)      # really not written
 
 
 def test_lean_grouped_step_is_bit_identical():
