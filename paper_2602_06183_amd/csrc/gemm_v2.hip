@@ -756,7 +756,20 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
         if (FP8 && EPI != 0 && ep.amax) note_amax_slots_seen(ep.amax, vmax_tile, amax_seen);
     } else {
         constexpr int EP = WN * 2 + 16;
+        constexpr int CH = WN / 8;
         unsigned char* scratch = smem + wave * (32 * EP);
+        // destination rows of the lane's 16 stores, looked up before the first store (loads and stores share one in-order counter: a look-up
+        // between two stores would wait for the earlier one)
+        int32_t io_map[FM][32 * CH / 64];
+        if (grp.out_row_map) {
+#pragma unroll
+            for (int a = 0; a < FM; ++a)
+#pragma unroll
+                for (int p = 0; p < 32 * CH / 64; ++p) {
+                    const int i = i0 + wm * WM + a * 32 + (lane + 64 * p) / CH;
+                    io_map[a][p] = i < Ra ? grp.out_row_map[i] : -1;
+                }
+        }
 #pragma unroll
         for (int a = 0; a < FM; ++a) {
 #pragma unroll
@@ -767,14 +780,13 @@ __global__ void __launch_bounds__(512) gemm_nt_v2_kernel(const uint16_t* __restr
                     *reinterpret_cast<uint16_t*>(scratch + row * EP + (b * 32 + l32) * 2) = (uint16_t)f2bf(FP8 ? acc[a][b][r] * alpha : acc[a][b][r]);
                 }
             __syncthreads();
-            constexpr int CH = WN / 8;
 #pragma unroll
             for (int p = 0; p < 32 * CH / 64; ++p) {
                 const int e = lane + 64 * p, row = e / CH, ch = e % CH;
                 const int i = i0 + wm * WM + a * 32 + row, j = j0 + wn * WN + ch * 8;
                 if (i < Ra && j < Rb) {
                     int64_t io = grp.map_logM ? ((int64_t)(i >> 2) << grp.map_logM) + 4 * expert_id + (i & 3) : i;
-                    if (grp.out_row_map) io = grp.out_row_map[i];
+                    if (grp.out_row_map) io = io_map[a][p];
                     if (io >= 0) *reinterpret_cast<uint4*>(out + io * ldo + j) = *reinterpret_cast<const uint4*>(scratch + row * EP + ch * 16);
                 }
             }
