@@ -235,6 +235,30 @@ def test_fp8_step_positions_are_those_of_the_bf16_rules_on_its_own_y1():
     assert np.array_equal(m1, got["w1_meta"])
 
 
+@pytest.mark.parametrize("M", [16, 32])
+def test_fp8_step_with_wide_blocks_keeps_the_bf16_rules_of_that_block_width(M):
+    """Table 5's wider blocks: on its own y1 the fp8 step's metadata, column indices and survivors are those of the bf16 compressor for
+    that M (so at most 2 of M entries survive), the codes are the survivors' quantisation, eq. (6) and the bf16 weight gradients are
+    the bf16 rules for that M, and eq. (3) is the dense product of the decoded, decompressed codes times the two scales."""
+    inp = _step_inputs(64, 32, 4 * M, seed=M)
+    ref = oracle.ffn_sparse_step_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"], V=64, M=M)
+    sc = _scales_for(inp, ref)
+    got = oracle.ffn_sparse_step_fp8_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"], sc, V=64, M=M)
+    vals, meta, colidx = oracle.sqrelu_vnm_compress(got["y1"], 64, M)
+    assert np.array_equal(meta, got["y2_meta"]) and np.array_equal(colidx, got["colidx"]) and np.array_equal(vals, got["y2_vals"])
+    assert np.array_equal(got["y2_codes"], fp8.quantize_fp8(vals, sc["y2"]))
+    assert got["y2_codes"].shape == (64, 2 * 4 * M // M) and colidx.shape == (1, 4, 4)
+    assert np.array_equal(got["dy1_vals"], oracle.dsqrelu_vnm(got["dy2"], got["y1"], meta, colidx, 64, M))
+    assert np.array_equal(got["dW2"], oracle.vnm_wgrad(vals, meta, colidx, inp["dY"], 0, 64, M))
+    assert np.array_equal(got["dW1"], oracle.vnm_wgrad(got["dy1_vals"], meta, colidx, inp["X"], 1, 64, M))
+    # eq. (3) on codes = the dense product of the decoded, decompressed codes
+    a = fp8.e4m3_decode(oracle.vnm_decompress(got["y2_codes"], meta, colidx, 64, M)).astype(np.float64)
+    w = fp8.e4m3_decode(got["w2q"]).astype(np.float64)
+    want = oracle.f64_to_bits(a @ w.T * np.float64(np.float32(sc["y2"]) * np.float32(sc["w2"])))
+    assert np.array_equal(got["y3"], want)
+    assert np.mean(a != 0) <= 2.0 / M
+
+
 def test_fp8_step_saturates_instead_of_overflowing():
     inp = _step_inputs(64, 32, 64, seed=7)
     ref = oracle.ffn_sparse_step_ref(inp["X"], inp["W1"], inp["W2"], inp["b1"], inp["dY"])
