@@ -523,10 +523,16 @@ def main():
         dense_out = torch.empty((T1, D1), dtype=torch.bfloat16, device="cuda")
         t_dense = ms_of(lambda: torch.mm(y1_1, W11, out=dense_out))
         venom = {"shape": "[%d, %d] x [%d, %d]" % (T1, F1, F1, D1), "dense_ms": round(t_dense, 4)}
+        sy8, sw8v = float(y1_1.float().clamp_min(0).square().max()) / 448.0, float(W11.float().abs().max()) / 448.0
+        w8v = sffn.quantize_fp8(W11, sw8v)
         for m in (8, 16, 32, 64):
             pack = sffn.sqrelu_vnm_compress(y1_1, 64, m)
             t = ms_of(lambda: sffn.vnm_spmm(pack[0], pack[1], pack[2], W11, 1, 64, m))
-            venom["64:2:%d" % m] = {"ms": round(t, 4), "speedup_vs_dense": round(t_dense / t, 3)}
+            pack8 = sffn.sqrelu_vnm_compress_fp8(y1_1, sy8, 64, m)          # the same contraction on E4M3 codes (Section 3.4, closing paragraph)
+            t8 = ms_of(lambda: sffn.vnm_spmm_fp8(pack8[0], pack8[1], pack8[2], sy8, w8v, sw8v, 1, 64, m))
+            venom["64:2:%d" % m] = {"ms": round(t, 4), "speedup_vs_dense": round(t_dense / t, 3), "fp8_ms": round(t8, 4),
+                                    "fp8_speedup_vs_dense_bf16": round(t_dense / t8, 3)}
+        del w8v
         del dense_out
         b1h1 = b11.to(torch.bfloat16)
         router = {"shape": "1b", "dense_y1_ms": round(ms_of(lambda: torch.addmm(b1h1, X1, W11.t(), out=y1_1)), 4)}

@@ -177,8 +177,12 @@ int vnm_wgrad(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_co
  *                           fp8 structured-sparse matrix cores; Xq [T, K] codes, Ws packed ([N, K/2], [N, K/8]); K a multiple of 128
  *   vnm_spmm_fp8            eqs. (3), (7): the V:N:M code matrix (a_codes [T, 2 Kfull/M]) times dense W codes, [N, Kfull]
  *                           (w_kmajor = 0) or [Kfull, N] (1, contiguous rows); Kfull a multiple of 128, T below 65536;
- *                           workspace: sffn_vnm_spmm_fp8_workspace_bytes()
- * The weight gradients (eqs. (5), (8), contraction over tokens) have no fp8 form here.  ffn_sparse_step_fp8 below is the whole step. */
+ *                           workspace: sffn_vnm_spmm_fp8_workspace_bytes().  M = 8 runs on the 256-token tile kernel of the fp8
+ *                           step after a small regrouping pass (w_kmajor = 1 then needs no transpose), M >= 16 with 4 Kfull / M a
+ *                           multiple of 128 gathers the kept rows of W (the wide-block fp8 step's kernel), anything else goes as
+ *                           plain 2:4 over all Kfull columns
+ * The weight gradients (eqs. (5), (8), contraction over tokens) have no stand-alone fp8 entry point; ffn_sparse_step_fp8 below is the
+ * whole step and can run them on the codes (SFFN_FLAG_FP8_WGRAD). */
 int quantize_fp8(const uint16_t* src, int64_t n, float scale, uint8_t* codes, float* amax, void* stream);
 int prune24_compress_fp8(const uint16_t* src, int64_t R, int64_t K, int64_t ld, int trans, int mode, float scale,
                          uint8_t* codes, uint8_t* meta, float* amax, void* stream);

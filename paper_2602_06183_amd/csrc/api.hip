@@ -382,8 +382,30 @@ int vnm_spmm_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* a
     uint8_t* c24 = ws;
     uint8_t* m24 = ws + up256((size_t)T * Kfull / 2);
     uint8_t* wt = m24 + up256((size_t)T * Kfull / 8);
-    LAUNCH(launch_vnm_to_24_fp8(a_codes, a_meta, a_colidx, T, Kfull, M, c24, m24, s), "vnm_spmm_fp8/to24");
     const uint8_t* W = Wq;
+    if (M == 8 && vnm8_gemm_fp8_ok(T, N, Kfull, N)) {
+        // the 256-token tile kernel of the fp8 step: the packed arrays regrouped into its units (one small pass), Wq contraction-major
+        uint8_t* vcb = c24;
+        uint8_t* mcb = m24;
+        uint8_t* cixt = m24 + up256((size_t)T * Kfull / 16);
+        if (!w_kmajor) {
+            LAUNCH(launch_transpose_u8(Wq, N, Kfull, Kfull, wt, s), "vnm_spmm_fp8/transpose");
+            W = wt;
+        }
+        LAUNCH(launch_vnm8_repack_fp8(a_codes, a_meta, a_colidx, T, Kfull, vcb, mcb, cixt, s), "vnm_spmm_fp8/repack");
+        LAUNCH(launch_vnm8_gemm_fp8(vcb, mcb, cixt, W, N, scale_a * scale_w, T, N, Kfull, out, N, s), "vnm_spmm_fp8/gemm");
+        return SFFN_OK;
+    }
+    if (M >= 16 && vnm_spmm_gather_fp8_ok(T, N, Kfull, M) && Kfull * N < ((int64_t)1 << 32)) {
+        // contract over the 4 Kfull / M kept columns only, gathering their rows of the [Kfull, N] codes (the fp8 step's kernel for wide blocks)
+        if (!w_kmajor) {
+            LAUNCH(launch_transpose_u8(Wq, N, Kfull, Kfull, wt, s), "vnm_spmm_fp8/transpose");
+            W = wt;
+        }
+        LAUNCH(launch_vnm_spmm_gather_fp8(a_codes, a_meta, a_colidx, W, N, scale_a * scale_w, T, N, Kfull, M, out, N, s), "vnm_spmm_fp8/gather");
+        return SFFN_OK;
+    }
+    LAUNCH(launch_vnm_to_24_fp8(a_codes, a_meta, a_colidx, T, Kfull, M, c24, m24, s), "vnm_spmm_fp8/to24");
     if (w_kmajor) {
         LAUNCH(launch_transpose_u8(Wq, Kfull, N, N, wt, s), "vnm_spmm_fp8/transpose");
         W = wt;

@@ -413,6 +413,41 @@ hipError_t launch_vnm_to_24_fp8(const uint8_t* codes, const uint8_t* meta, const
     return hipGetLastError();
 }
 
+// The canonical fp8 V:2:8 arrays (codes [T, F/4], meta [T, F/16], colidx [T/64, F/8, 4]) regrouped into the units of the fp8 form of the V:2:8
+// activation GEMM (gemm_vnm8.hip; the fused epilogues of the fp8 step write them directly): one thread per (token, 128 hidden units) moves 32
+// codes and 8 metadata bytes; the first 16 threads of a token block also build the 16 offset words of their (token block, 128 hidden units).
+__global__ void __launch_bounds__(256) vnm8_repack_fp8_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ meta,
+                                                             const uint8_t* __restrict__ colidx, int64_t T, int F, uint8_t* __restrict__ vcb,
+                                                             uint8_t* __restrict__ mcb, uint8_t* __restrict__ cixt) {
+    const int KS = F >> 7;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= T * KS) return;
+    const int64_t t = i / KS;
+    const int kt = (int)(i - t * KS);
+    const uint4* src = reinterpret_cast<const uint4*>(codes + t * (F >> 2) + kt * 32);
+    uint4* dst = reinterpret_cast<uint4*>(vcb + vcb8_off(t, (int64_t)kt * 16, F));
+    dst[0] = src[0];
+    dst[1] = src[1];
+    *reinterpret_cast<uint2*>(mcb + mcb8_off(t, (int64_t)kt * 2, F)) = *reinterpret_cast<const uint2*>(meta + t * (F >> 4) + kt * 8);
+    const int q = (int)(t & 63);
+    if (q < 16) {       // word (h, p), byte j = kept column p % 4 of column block 8 (j / 2) + 4 h + 2 (j % 2) + p / 4
+        const int h = q >> 3, p = q & 7;
+        const uint8_t* c = colidx + ((t >> 6) * (F >> 3) + kt * 16) * 4;
+        uint32_t dw = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dw |= (uint32_t)c[(8 * (j >> 1) + 4 * h + 2 * (j & 1) + (p >> 2)) * 4 + (p & 3)] << (8 * j);
+        *reinterpret_cast<uint32_t*>(cixt + cixt8_off(t >> 6, kt, T >> 6) + q * 4) = dw;
+    }
+}
+
+hipError_t launch_vnm8_repack_fp8(const uint8_t* codes, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F, uint8_t* vcb, uint8_t* mcb,
+                                  uint8_t* cixt, hipStream_t s) {
+    if (T % 64 != 0 || F % 128 != 0) return hipErrorInvalidValue;
+    const int64_t n = T * (F / 128);
+    hipLaunchKernelGGL(vnm8_repack_fp8_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, codes, meta, colidx, T, (int)F, vcb, mcb, cixt);
+    return hipGetLastError();
+}
+
 hipError_t launch_transpose_u8(const uint8_t* in, int64_t R, int64_t C, int64_t ld, uint8_t* out, hipStream_t s) {
     hipLaunchKernelGGL(transpose_u8_kernel, dim3((unsigned)(C / 64), (unsigned)(R / 64)), dim3(256), 0, s, in, R, C, ld, out);
     return hipGetLastError();

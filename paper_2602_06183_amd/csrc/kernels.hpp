@@ -110,6 +110,9 @@ hipError_t launch_vnm8_repack(const uint16_t* vals, const uint8_t* meta, const u
                               uint8_t* cixt, hipStream_t s);
 // (fp8 step: codes; F a multiple of 128, Wq = [F, ldw bytes], out = bf16(alpha * sum); the arrays in the layouts of vcb8_off, mcb8_off, cixt8_off)
 bool vnm8_gemm_fp8_ok(int64_t T, int64_t N, int64_t F, int64_t ldw);
+// fp8.hip: the canonical fp8 V:2:8 arrays (codes [T, F/4], meta, colidx) regrouped into those units; F a multiple of 128
+hipError_t launch_vnm8_repack_fp8(const uint8_t* codes, const uint8_t* meta, const uint8_t* colidx, int64_t T, int64_t F, uint8_t* vcb, uint8_t* mcb,
+                                  uint8_t* cixt, hipStream_t s);
 hipError_t launch_vnm8_gemm_fp8(const uint8_t* vcb, const uint8_t* mcb, const uint8_t* cixt, const uint8_t* Wq, int64_t ldw, float alpha, int64_t T,
                                 int64_t N, int64_t F, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
 // The same on E4M3 codes: a_codes [T, 2 F / M] + the same metadata and column offsets, Wq = codes [F, ldw bytes], out = bf16(alpha * sum);

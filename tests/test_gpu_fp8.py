@@ -112,8 +112,8 @@ def test_spmm24_fp8_exact_on_small_integers():
             assert np.array_equal(oracle.bits_to_f32(got), oracle.bits_to_f32(oracle.vnm_spmm(av, u8(am), u8(ai), w, kmaj, 64, M)))
 
 
-@pytest.mark.parametrize("M", [8, 16])
-@pytest.mark.parametrize("T,F,D", [(64, 128, 64), (192, 384, 320), (256, 2048, 192)])
+@pytest.mark.parametrize("M", [8, 16, 32, 64])
+@pytest.mark.parametrize("T,F,D", [(64, 128, 64), (192, 384, 320), (256, 2048, 192), (576, 4096, 320)])
 def test_vnm_spmm_fp8(T, F, D, M):
     rng = np.random.default_rng(T + 3 * F + 7 * D + M)
     y1 = bf16_bits_from_f32(rng.standard_normal((T, F), dtype=np.float32) - np.float32(0.8))
