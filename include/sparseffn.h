@@ -75,6 +75,14 @@ typedef struct sffn_cfg {
  * step reads its own operand layouts, and Y3, dX, dW1, dW2, y2_meta, colidx, y1_kept are the same bits with or without the flag.  Ignored
  * by the unfused path. */
 #define SFFN_FLAG_LEAN 8
+/* ffn_sparse_step, ffn_sparse_step_grouped, ffn_sparse_step_fp8, ffn_sparse_step_fp8_grouped (not the unfused path, not the router
+ * steps: SFFN_EUNSUPPORTED there): the weights are already packed.  Section 3.4 notes that the conversion of a weight to 2:4 is paid
+ * once per optimizer step and amortised over the micro-batches that pass through the layer before the weights change.  The caller
+ * promises that the previous call on this workspace ran without this flag on the same cfg (apart from this flag), W1 and W2 (fp8: and
+ * the same scales w1, w2), and that nothing else has written the workspace since; the step then skips Alg. 1 line 4 and Alg. 2 line 2
+ * (both pruning passes, with them the W2.T copy and, fp8, the weight quantisation) and reads what that call left.  Every output is the
+ * same bits as without the flag.  The library cannot check the promise.  fp8: amax[1], amax[2] (w1, w2) come back as 0. */
+#define SFFN_FLAG_WEIGHTS_PACKED 16
 
 /* Byte offsets, inside the workspace of ffn_sparse_step, of the tensors Alg. 2 line 1 saves
  * from the forward pass and of the other intermediates (all filled when the step returns). */
@@ -292,7 +300,8 @@ int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint1
 
 /* Alg. 1 + Alg. 2, one call: X [T,D], W1 [F,D], W2 [D,F], b1 fp32 [F] or NULL, dY [T,D] ->
  * Y3 [T,D], dX [T,D], dW1 [F,D], dW2 [D,F]; intermediates land in `workspace` at the offsets of
- * sffn_workspace_layout().  Both weight matrices are re-pruned inside the call.
+ * sffn_workspace_layout().  Both weight matrices are re-pruned inside the call (SFFN_FLAG_WEIGHTS_PACKED: a later micro-batch
+ * of the same optimizer step reuses what the previous call packed).
  * cfg->M = 16, 32 or 64 (Table 5): the same algorithm and the same fusion; eqs. (3), (7) contract only the kept rows of
  * W2.T / W1 (see vnm_spmm), and the packed activation tensors have the sizes given above.  Shapes whose 4 F / M is not a
  * multiple of 64 or exceeds 7168, and calls with SFFN_FLAG_UNFUSED, run eqs. (2), (6) as separate kernels instead: the dense

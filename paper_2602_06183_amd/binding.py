@@ -187,6 +187,7 @@ FLAG_KEEP_DENSE = 1
 FLAG_UNFUSED = 2
 FLAG_FP8_WGRAD = 4
 FLAG_LEAN = 8
+FLAG_WEIGHTS_PACKED = 16
 
 
 def dense_sqrelu(y1, out):
@@ -206,6 +207,14 @@ def dense_dsqrelu(dy2, y1, out):
 
 def _cfg(T, D, F, mode=MODE_HARD, V=64, M=8, flags=0):
     return _Cfg(T, D, F, V, M, mode, flags)
+
+
+def _cfg_with(cfg, weights_packed):
+    """The step's configuration, with SFFN_FLAG_WEIGHTS_PACKED added when the caller says that the previous call on this object ran on
+    the same W1 / W2 (micro-batches between two optimizer steps, Section 3.4): the pruning passes are then skipped."""
+    if not weights_packed:
+        return cfg
+    return _Cfg(cfg.T, cfg.D, cfg.F, cfg.V, cfg.M, cfg.mode, cfg.flags | FLAG_WEIGHTS_PACKED)
 
 
 def _flags(keep_dense, unfused=False, lean=False):
@@ -362,14 +371,14 @@ class FfnStep:
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
         self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
 
-    def __call__(self, X, W1, W2, b1, dY):
+    def __call__(self, X, W1, W2, b1, dY, weights_packed=False):
         T, D, F = self.T, self.D, self.F
         _want("ffn_sparse_step: X", X, (T, D), _BF16)
         _want("ffn_sparse_step: W1", W1, (F, D), _BF16)
         _want("ffn_sparse_step: W2", W2, (D, F), _BF16)
         _want("ffn_sparse_step: b1", b1, (F,), _F32, optional=True)
         _want("ffn_sparse_step: dY", dY, (T, D), _BF16)
-        _check(load().ffn_sparse_step(ctypes.byref(self.cfg), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY), _ptr(self.Y3),
+        _check(load().ffn_sparse_step(ctypes.byref(_cfg_with(self.cfg, weights_packed)), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY), _ptr(self.Y3),
                                       _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
 
@@ -412,14 +421,14 @@ class FfnStepGrouped:
         self.Y3, self.dX = _bf16((self.T, D), device), _bf16((self.T, D), device)
         self.dW1, self.dW2 = _bf16((self.E, F, D), device), _bf16((self.E, D, F), device)
 
-    def __call__(self, X, W1, W2, b1, dY):
+    def __call__(self, X, W1, W2, b1, dY, weights_packed=False):
         T, D, F, E = self.T, self.D, self.F, self.E
         _want("ffn_sparse_step_grouped: X", X, (T, D), _BF16)
         _want("ffn_sparse_step_grouped: W1", W1, (E, F, D), _BF16)
         _want("ffn_sparse_step_grouped: W2", W2, (E, D, F), _BF16)
         _want("ffn_sparse_step_grouped: b1", b1, (E, F), _F32, optional=True)
         _want("ffn_sparse_step_grouped: dY", dY, (T, D), _BF16)
-        _check(load().ffn_sparse_step_grouped(ctypes.byref(self.cfg), self.E, self.seg_c, _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1),
+        _check(load().ffn_sparse_step_grouped(ctypes.byref(_cfg_with(self.cfg, weights_packed)), self.E, self.seg_c, _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1),
                                               _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws),
                                               self.layout["total"], _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
@@ -549,14 +558,14 @@ class FfnStepFp8:
         a = self.amax[:6].tolist()
         return dict(zip(("x", "w1", "w2", "y2", "dy", "dy1"), a))
 
-    def __call__(self, X, W1, W2, b1, dY):
+    def __call__(self, X, W1, W2, b1, dY, weights_packed=False):
         T, D, F = self.T, self.D, self.F
         _want("ffn_sparse_step_fp8: X", X, (T, D), _BF16)
         _want("ffn_sparse_step_fp8: W1", W1, (F, D), _BF16)
         _want("ffn_sparse_step_fp8: W2", W2, (D, F), _BF16)
         _want("ffn_sparse_step_fp8: b1", b1, (F,), _F32, optional=True)
         _want("ffn_sparse_step_fp8: dY", dY, (T, D), _BF16)
-        _check(load().ffn_sparse_step_fp8(ctypes.byref(self.cfg), ctypes.byref(self.scales), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY),
+        _check(load().ffn_sparse_step_fp8(ctypes.byref(_cfg_with(self.cfg, weights_packed)), ctypes.byref(self.scales), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY),
                                           _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _ptr(self.amax), _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
 
@@ -603,14 +612,14 @@ class FfnStepFp8Grouped(FfnStepFp8):
         self.dW1, self.dW2 = _bf16((self.E, F, D), device), _bf16((self.E, D, F), device)
         self.amax = torch.zeros((8,), dtype=torch.float32, device=device)
 
-    def __call__(self, X, W1, W2, b1, dY):
+    def __call__(self, X, W1, W2, b1, dY, weights_packed=False):
         T, D, F, E = self.T, self.D, self.F, self.E
         _want("ffn_sparse_step_fp8_grouped: X", X, (T, D), _BF16)
         _want("ffn_sparse_step_fp8_grouped: W1", W1, (E, F, D), _BF16)
         _want("ffn_sparse_step_fp8_grouped: W2", W2, (E, D, F), _BF16)
         _want("ffn_sparse_step_fp8_grouped: b1", b1, (E, F), _F32, optional=True)
         _want("ffn_sparse_step_fp8_grouped: dY", dY, (T, D), _BF16)
-        _check(load().ffn_sparse_step_fp8_grouped(ctypes.byref(self.cfg), ctypes.byref(self.scales), self.E, self.seg_c, _ptr(X), _ptr(W1), _ptr(W2),
+        _check(load().ffn_sparse_step_fp8_grouped(ctypes.byref(_cfg_with(self.cfg, weights_packed)), ctypes.byref(self.scales), self.E, self.seg_c, _ptr(X), _ptr(W1), _ptr(W2),
                                                   _ptr(b1), _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws),
                                                   self.layout["total"], _ptr(self.amax), _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2

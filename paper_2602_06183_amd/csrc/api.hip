@@ -424,7 +424,7 @@ struct Fp8Layout {
 bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L, int n_experts = 1) {
     if (!c || !mult64(c->T) || !mult128(c->D) || !mult128(c->F) || c->V != 64 || n_experts < 1) return false;
     if (c->M != 8 && !(vnm_ok(c->V, c->M) && vnm_spmm_gather_fp8_ok(c->T, c->D, c->F, c->M))) return false;
-    if (c->flags & ~(SFFN_FLAG_KEEP_DENSE | SFFN_FLAG_FP8_WGRAD | SFFN_FLAG_LEAN)) return false;
+    if (c->flags & ~(SFFN_FLAG_KEEP_DENSE | SFFN_FLAG_FP8_WGRAD | SFFN_FLAG_LEAN | SFFN_FLAG_WEIGHTS_PACKED)) return false;
     const bool dense = (c->flags & SFFN_FLAG_KEEP_DENSE) != 0;
     const size_t T = c->T, D = c->D, F = (size_t)c->F * n_experts, TF = T * (size_t)c->F, M = (size_t)c->M;
     size_t off = 0;
@@ -458,7 +458,7 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "ffn_sparse_step_fp8: only V = 64 with M in {8, 16, 32, 64} is built");
     REQUIRE(make_fp8_layout(cfg, &L, n_experts), SFFN_EINVAL,
             "ffn_sparse_step_fp8: T must be a positive multiple of 64, D and F of 128 (M >= 16: 4 F / M a multiple of 128); flags: "
-            "SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD, SFFN_FLAG_LEAN");
+            "SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD, SFFN_FLAG_LEAN, SFFN_FLAG_WEIGHTS_PACKED");
     REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_sparse_step_fp8: unknown mode");
     REQUIRE(X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_sparse_step_fp8: null pointer");
     REQUIRE(aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(dY) && aligned16(Y3) && aligned16(dX) && aligned16(dW1) && aligned16(dW2) &&
@@ -527,7 +527,8 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
         STAGE(launch_quantize_fp8_blocked(X, T, D, D, ix, xq, s, ax), "step/quantize(X)");
     }
     // W1 in one pass per expert: pruned (canonical + blocked codes) for eq. (1), and the un-pruned W1 as codes for eq. (7)
-    for (int64_t e = 0; e < E; ++e)
+    const bool packed = (cfg->flags & SFFN_FLAG_WEIGHTS_PACKED) != 0;    // both weight passes skipped: the previous call's codes are still in the workspace
+    for (int64_t e = 0; e < E && !packed; ++e)
         STAGE(launch_prune24_fp8_step(W1 + e * F * D, F, D, D, 0, cfg->mode, iw1, w1c ? w1c + e * F * D / 2 : nullptr, w1m ? w1m + e * F * D / 8 : nullptr,
                                       w1b + e * F * D / 2, w1mb + e * F * D / 8, s, aw1, w1q + e * F * D), "step/prune24_fp8(W1)+quantize(W1)");
     {   // eq. (1) on codes, then eq. (2) + V:N:M compression on the bf16 tile; the survivors leave as codes (and in bf16 for eq. (5))
@@ -537,7 +538,7 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
         if (!wide) { ep.vcb = (uint16_t*)vcb; ep.mcb = mcb; ep.cixt = cixt; }
         STAGE(launch_gemm_fp8_blocked(w1b, w1mb, xq, b1, sc->x * sc->w1, F, T, D, y1, F, &ep, s, gp), "step/y1+sqrelu_vnm_compress");
     }
-    for (int64_t e = 0; e < E; ++e)
+    for (int64_t e = 0; e < E && !packed; ++e)
         STAGE(launch_prune24_fp8_step(W2 + e * D * F, F, D, F, 1, cfg->mode, iw2, w2c ? w2c + e * F * D / 2 : nullptr, w2m ? w2m + e * F * D / 8 : nullptr,
                                       w2b + e * F * D / 2, w2mb + e * F * D / 8, s, aw2, w2tq + e * F * D), "step/prune24_fp8(W2.T)+quantize(W2.T)");
     if (wide) STAGE(launch_vnm_spmm_gather_fp8(y2c, y2m, cix, w2tq, D, sc->y2 * sc->w2, T, D, F, M, Y3, D, s, gr), "step/y3");      // eq. (3)
@@ -736,6 +737,7 @@ static int run_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, cons
     RouterLayout L;
     REQUIRE(make_router_layout(cfg, &L), SFFN_EINVAL, "ffn_router_step: T > 0, D and F positive multiples of 64, 4F/M a multiple of 64");
     REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_router_step: unknown mode");
+    REQUIRE(!(cfg->flags & SFFN_FLAG_WEIGHTS_PACKED), SFFN_EUNSUPPORTED, "ffn_router_step: SFFN_FLAG_WEIGHTS_PACKED is not built for the router's step");
     const int64_t T = cfg->T, D = cfg->D, F = cfg->F;
     const int M = cfg->M, E = M / 4;
     const int64_t Kc = 4 * F / M, rows = sffn_venom_rows(T, M);
@@ -926,6 +928,10 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     uint8_t* kmask = ws + L.kmask;
     uint16_t* ykept = (uint16_t*)(ws + L.pub.y1_kept);
     const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
+    // SFFN_FLAG_WEIGHTS_PACKED: the workspace still holds the packed weights (and W2.T) of the previous call: no pruning passes (Section 3.4:
+    // the conversion is paid once per optimizer step, not once per micro-batch)
+    const bool packed = (cfg->flags & SFFN_FLAG_WEIGHTS_PACKED) != 0;
+    REQUIRE(!packed || cfg->M == 8 || fused_wide(cfg), SFFN_EUNSUPPORTED, "ffn_sparse_step: SFFN_FLAG_WEIGHTS_PACKED is not built for the unfused path");
     if (fused_wide(cfg)) {
         // Blocks of M = 16, 32, 64 columns (Table 5), fused like the M = 8 step: eq. (2) + compression in the epilogue of eq. (1), eq. (6)
         // in the epilogue of eq. (4) (the dense y1 / dy2 stay in LDS), eqs. (3), (7) on the kept rows of W2.T / W1 only (the pruning
@@ -943,13 +949,13 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
         if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
         STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
         const bool lean_w = (cfg->flags & SFFN_FLAG_LEAN) != 0;        // no canonical copies of the packed weights (the packed activations stay: eqs. (3), (7) read them)
-        STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, lean_w ? nullptr : w1v, lean_w ? nullptr : w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
+        if (!packed) STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, lean_w ? nullptr : w1v, lean_w ? nullptr : w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
         {
             VnmEpilogue ep;
             ep.mode = 5; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = y2v; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept; ep.at = atb;
             STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s, gp), "step/y1+sqrelu_vnm_compress");         // eqs. (1), (2), Section 2.3
         }
-        STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, lean_w ? nullptr : w2v, lean_w ? nullptr : w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
+        if (!packed) STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, lean_w ? nullptr : w2v, lean_w ? nullptr : w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
         STAGE(launch_vnm_spmm_gather(y2v, y2m, cix, w2t, D, T, D, F, M, Y3, D, s, gr), "step/y3");                              // eq. (3)
         STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
         STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");                                       // eq. (5)
@@ -1033,14 +1039,14 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     g_dense.b_stride = F * D;
     STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
     // row pruning is per row, so the E stacked [F, D] matrices are one [E * F, D] matrix
-    STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, lean ? nullptr : w1v, lean ? nullptr : w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
+    if (!packed) STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, lean ? nullptr : w1v, lean ? nullptr : w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
     {   // eq. (1), then eq. (2) + V:N:M compression on the tile while it is still in LDS
         VnmEpilogue ep;
         ep.mode = 1; ep.store_dense = keep_dense; ep.vals = lean ? nullptr : y2v; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
         ep.vcb = vcb; ep.mcb = mcb; ep.cixt = cixt; ep.at = atb;
         STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s, gp), "step/y1+sqrelu_vnm_compress");
     }
-    STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, lean ? nullptr : w2v, lean ? nullptr : w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
+    if (!packed) STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, lean ? nullptr : w2v, lean ? nullptr : w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
     STAGE(launch_vnm8_gemm(vcb, mcb, cixt, w2t, D, T, D, F, Y3, D, s, gd), "step/y3");                         // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
     STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");

@@ -71,6 +71,8 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     assert len(lib.sffn_last_error()) > 0
     huge = binding._Cfg(64, 32768, 65536, 64, 8, 0, 0)                    # a 4 GiB weight matrix: beyond the 32-bit offsets of the V:2:8 kernel's loads
     assert lib.ffn_sparse_step(ctypes.byref(huge), *args, fake, 1 << 50, None) == -2
+    # SFFN_FLAG_WEIGHTS_PACKED (16) exists for the fused paths only: the unfused wide-block path (flag 2) refuses it before any launch
+    assert lib.ffn_sparse_step(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 16, 0, 2 | 16)), *args, fake, 1 << 40, None) == -2
     # the fp8 step: scales are a host struct; shapes, flags, scales and the workspace are checked before anything is enqueued
     sc = binding._Fp8Scales(1.0, 1.0, 1.0, 1.0, 1.0, 1.0)
     assert lib.ffn_sparse_step_fp8(ctypes.byref(cfg), None, *args, fake, 1 << 40, None, None) == -1                 # no scales
@@ -138,6 +140,7 @@ def test_router_entry_points_validate_on_the_host():
     assert lib.ffn_router_step(ctypes.byref(bad), ok, *args, fake, big, None) == -1
     m12 = binding._Cfg(100, 64, 1024, 64, 12, 0, 0)
     assert lib.ffn_router_step(ctypes.byref(m12), ok, *args, fake, big, None) == -2
+    assert lib.ffn_router_step(ctypes.byref(binding._Cfg(cfg.T, cfg.D, cfg.F, 64, cfg.M, 0, 16)), ok, *args, fake, big, None) == -2     # no packed-weights form
     assert lib.sffn_router_full_workspace_bytes(ctypes.byref(cfg)) > lib.sffn_router_workspace_bytes(ctypes.byref(cfg))
     assert lib.sffn_router_full_workspace_bytes(ctypes.byref(bad)) == 0
     assert lib.ffn_router_full_step(ctypes.byref(cfg), *args, fake, 16, None) == -3

@@ -369,6 +369,28 @@ def test_fp8_step_delayed_scaling_round_trip():
     assert np.abs(fp8.e4m3_decode(s["y2_codes"].cpu().numpy())).max() == 448.0
 
 
+@pytest.mark.parametrize("M,wgrad_fp8,lean", [(8, False, False), (8, True, True), (16, True, False)])
+def test_fp8_step_on_packed_weights_is_bit_identical(M, wgrad_fp8, lean):
+    """SFFN_FLAG_WEIGHTS_PACKED for the fp8 step (Section 3.4: conversion once per optimizer step): the second micro-batch runs neither
+    weight pass - the weights handed to it are garbage and go unread - and gives the bits of a full call; the weights' maxima come back 0."""
+    T, D, F = 320, 256, 1024
+    a, b = make_ffn_inputs(T, D, F, seed=31), make_ffn_inputs(T, D, F, seed=32)
+    sc = dict(x=5.0 / 448, w1=0.1 / 448, w2=0.1 / 448, y2=8.0 / 448, dy=5.0 / 448, dy1=2.0 / 448)
+    W1, W2, b1 = to_dev(a["W1"]), to_dev(a["W2"]), to_dev(a["b1"])
+    step = sffn.FfnStepFp8(T, D, F, sc, sffn.MODE_SOFT, wgrad_fp8=wgrad_fp8, lean=lean, M=M)
+    fresh = sffn.FfnStepFp8(T, D, F, sc, sffn.MODE_SOFT, wgrad_fp8=wgrad_fp8, lean=lean, M=M)
+    step(to_dev(a["X"]), W1, W2, b1, to_dev(a["dY"]))
+    junk = torch.full_like(W1, 7.0)
+    got = [to_bits(t).copy() for t in step(to_dev(b["X"]), junk, junk.view(D, F), b1, to_dev(b["dY"]), weights_packed=True)]
+    want = [to_bits(t).copy() for t in fresh(to_dev(b["X"]), W1, W2, b1, to_dev(b["dY"]))]
+    for name, x, y in zip(("Y3", "dX", "dW1", "dW2"), got, want):
+        assert np.array_equal(x, y), name
+    ga, wa = step.amax_dict(), fresh.amax_dict()
+    assert ga["w1"] == 0.0 and ga["w2"] == 0.0 and wa["w1"] > 0.0
+    for k in ("x", "y2", "dy", "dy1"):
+        assert ga[k] == wa[k], k
+
+
 @pytest.mark.parametrize("wgrad_fp8", [False, True])
 def test_grouped_fp8_step_matches_oracle_per_expert(wgrad_fp8):
     """The mixture-of-experts form of the fp8 step (uneven segments, one of them empty): every expert's share is checked

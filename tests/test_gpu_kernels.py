@@ -699,6 +699,38 @@ def test_lean_wide_block_step_is_bit_identical(M):
     assert np.all(to_bits(sb["w1_vals"]) == 0xA5A5) and np.all(to_bits(sb["w2t_vals"]) == 0xA5A5)      # really not written
 
 
+@pytest.mark.parametrize("M,lean", [(8, False), (8, True), (16, False), (64, True)])
+def test_step_on_packed_weights_is_bit_identical(M, lean):
+    """SFFN_FLAG_WEIGHTS_PACKED (Section 3.4: a weight is converted once per optimizer step, not once per micro-batch): the second micro-batch
+    skips both pruning passes and must give the bits of a full call; the weights handed to that call are garbage, to show they are not read
+    by the passes that were skipped (eq. (7) still reads the real W1)."""
+    T, D, F = 320, 256, 1024
+    a, b = make_ffn_inputs(T, D, F, seed=21), make_ffn_inputs(T, D, F, seed=22)
+    W1, W2, b1 = to_dev(a["W1"]), to_dev(a["W2"]), to_dev(a["b1"])
+    step, fresh = sffn.FfnStep(T, D, F, sffn.MODE_SOFT, M=M, lean=lean), sffn.FfnStep(T, D, F, sffn.MODE_SOFT, M=M, lean=lean)
+    step(to_dev(a["X"]), W1, W2, b1, to_dev(a["dY"]))                                       # micro-batch 1 packs the weights
+    got = [to_bits(t).copy() for t in step(to_dev(b["X"]), W1, torch.full_like(W2, 3.0), b1, to_dev(b["dY"]), weights_packed=True)]
+    want = [to_bits(t).copy() for t in fresh(to_dev(b["X"]), W1, W2, b1, to_dev(b["dY"]))]
+    for name, x, y in zip(("Y3", "dX", "dW1", "dW2"), got, want):
+        assert np.array_equal(x, y), name
+    sa, sb = step.saved(), fresh.saved()
+    for k in ("y2_meta", "colidx", "y1_kept") + (() if lean else ("w1_vals", "w2t_meta", "y2_vals", "dy1_vals")):
+        assert np.array_equal(to_bits(sa[k]), to_bits(sb[k])), k
+
+
+def test_grouped_step_on_packed_weights_is_bit_identical():
+    D, F = 192, 320
+    m = make_moe_inputs(n_tokens=900, n_experts=4, top_k=2, D=D, F=F, seed=2)
+    dev = {k: to_dev(m[k]) for k in ("X", "W1", "W2", "b1", "dY")}
+    step, fresh = sffn.FfnStepGrouped(m["seg"], D, F), sffn.FfnStepGrouped(m["seg"], D, F)
+    step(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    X2, dY2 = torch.flip(dev["X"], (0,)).contiguous(), torch.flip(dev["dY"], (1,)).contiguous()
+    got = [to_bits(t).copy() for t in step(X2, dev["W1"], dev["W2"], dev["b1"], dY2, weights_packed=True)]
+    want = [to_bits(t).copy() for t in fresh(X2, dev["W1"], dev["W2"], dev["b1"], dY2)]
+    for name, x, y in zip(("Y3", "dX", "dW1", "dW2"), got, want):
+        assert np.array_equal(x, y), name
+
+
 def test_lean_grouped_step_is_bit_identical():
     D, F = 192, 320
     m = make_moe_inputs(n_tokens=900, n_experts=4, top_k=2, D=D, F=F, seed=2)
