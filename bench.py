@@ -368,7 +368,7 @@ def main():
         # a narrower layer of the same d_model: the first Fs hidden units (whole V:N:M column blocks; hidden units only meet in
         # the sums of Y3 and dX) on the first Ts tokens, sized for roughly 10-30 s of numpy work
         Fs = F if F * D <= (1 << 25) else max(512, ((1 << 25) // D) // 64 * 64)
-        Ts = min(T, max(64, (int(5.0e11 / (12.0 * D * Fs)) // 64) * 64))
+        Ts = min(T, max(64, (int(1.5e12 / (12.0 * D * Fs)) // 64) * 64))
         inp = hw.host
         w1o, w2o, b1o = (inp[k][0] if hw.moe else inp[k] for k in ("W1", "W2", "b1"))    # moe: expert 0 on its first tokens
         w1o, w2o, b1o = w1o[:Fs], np.ascontiguousarray(w2o[:, :Fs]), b1o[:Fs]

@@ -892,6 +892,8 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     REQUIRE(cfg->M == 8 || fused_wide(cfg) || (seg == nullptr && n_experts == 1), SFFN_EUNSUPPORTED,
             "ffn_sparse_step_grouped: blocks of 16 / 32 / 64 columns need 4 F / M to be a multiple of 64 and at most 7168 (and no SFFN_FLAG_UNFUSED)");
     REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_sparse_step: unknown mode");
+    REQUIRE(!(cfg->flags & ~(SFFN_FLAG_KEEP_DENSE | SFFN_FLAG_UNFUSED | SFFN_FLAG_FP8_WGRAD | SFFN_FLAG_LEAN | SFFN_FLAG_WEIGHTS_PACKED)), SFFN_EINVAL,
+            "ffn_sparse_step: unknown flag");
     REQUIRE(aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(b1) && aligned16(dY) && aligned16(Y3) && aligned16(dX) &&
                 aligned16(dW1) && aligned16(dW2) && aligned16(workspace),
             SFFN_EINVAL, "ffn_sparse_step: pointers must be 16-byte aligned");

@@ -71,6 +71,7 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     assert len(lib.sffn_last_error()) > 0
     huge = binding._Cfg(64, 32768, 65536, 64, 8, 0, 0)                    # a 4 GiB weight matrix: beyond the 32-bit offsets of the V:2:8 kernel's loads
     assert lib.ffn_sparse_step(ctypes.byref(huge), *args, fake, 1 << 50, None) == -2
+    assert lib.ffn_sparse_step(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 8, 0, 64)), *args, fake, 1 << 40, None) == -1        # unknown flag
     # SFFN_FLAG_WEIGHTS_PACKED (16) exists for the fused paths only: the unfused wide-block path (flag 2) refuses it before any launch
     assert lib.ffn_sparse_step(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 16, 0, 2 | 16)), *args, fake, 1 << 40, None) == -2
     # the fp8 step: scales are a host struct; shapes, flags, scales and the workspace are checked before anything is enqueued
