@@ -112,6 +112,15 @@ def load():
     lib.ffn_sparse_step_fp8.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Scales), p, p, p, p, p, p, p, p, p, p, sz, p, p]
     lib.sffn_fp8_grouped_workspace_layout.argtypes = [ctypes.POINTER(_Cfg), i32, ctypes.POINTER(_Fp8Layout)]
     lib.ffn_sparse_step_fp8_grouped.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Scales), i32, p, p, p, p, p, p, p, p, p, p, p, sz, p, p]
+    cfgp, scp, segp = ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Scales), ctypes.POINTER(ctypes.c_int64)
+    lib.ffn_sparse_forward.argtypes = [cfgp] + [p] * 5 + [p, sz, p]
+    lib.ffn_sparse_backward.argtypes = [cfgp] + [p] * 5 + [p, sz, p]
+    lib.ffn_sparse_forward_grouped.argtypes = [cfgp, i32, segp] + [p] * 5 + [p, sz, p]
+    lib.ffn_sparse_backward_grouped.argtypes = [cfgp, i32, segp] + [p] * 5 + [p, sz, p]
+    lib.ffn_sparse_forward_fp8.argtypes = [cfgp, scp] + [p] * 5 + [p, sz, p, p]
+    lib.ffn_sparse_backward_fp8.argtypes = [cfgp, scp] + [p] * 4 + [p, sz, p, p]
+    lib.ffn_sparse_forward_fp8_grouped.argtypes = [cfgp, scp, i32, segp] + [p] * 5 + [p, sz, p, p]
+    lib.ffn_sparse_backward_fp8_grouped.argtypes = [cfgp, scp, i32, segp] + [p] * 4 + [p, sz, p, p]
     lib.sffn_dense_sqrelu.argtypes = [p, p, i64, p]
     lib.sffn_dense_dsqrelu.argtypes = [p, p, p, i64, p]
     lib.sffn_profile_enable.argtypes = [i32]
@@ -382,6 +391,26 @@ class FfnStep:
                                       _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
 
+    def forward(self, X, W1, W2, b1, weights_packed=False):
+        """Alg. 1 alone (ffn_sparse_forward): Y3; what the backward pass needs stays in this object's workspace."""
+        T, D, F = self.T, self.D, self.F
+        _want("ffn_sparse_forward: X", X, (T, D), _BF16)
+        _want("ffn_sparse_forward: W1", W1, (F, D), _BF16)
+        _want("ffn_sparse_forward: W2", W2, (D, F), _BF16)
+        _want("ffn_sparse_forward: b1", b1, (F,), _F32, optional=True)
+        _check(load().ffn_sparse_forward(ctypes.byref(_cfg_with(self.cfg, weights_packed)), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(self.Y3),
+                                         _ptr(self.ws), self.layout["total"], _stream()))
+        return self.Y3
+
+    def backward(self, W1, dY):
+        """Alg. 2 alone (ffn_sparse_backward) on what the last forward() of this object left: dX, dW1, dW2."""
+        T, D, F = self.T, self.D, self.F
+        _want("ffn_sparse_backward: W1", W1, (F, D), _BF16)
+        _want("ffn_sparse_backward: dY", dY, (T, D), _BF16)
+        _check(load().ffn_sparse_backward(ctypes.byref(self.cfg), _ptr(W1), _ptr(dY), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2),
+                                          _ptr(self.ws), self.layout["total"], _stream()))
+        return self.dX, self.dW1, self.dW2
+
     def saved(self):
         """Views of the intermediates the step leaves in its workspace (Alg. 2 line 1 and friends)."""
         T, D, F, M, L = self.T, self.D, self.F, self.M, self.layout
@@ -432,6 +461,26 @@ class FfnStepGrouped:
                                               _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws),
                                               self.layout["total"], _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
+
+    def forward(self, X, W1, W2, b1, weights_packed=False):
+        """Alg. 1 alone for every expert (ffn_sparse_forward_grouped)."""
+        T, D, F, E = self.T, self.D, self.F, self.E
+        _want("ffn_sparse_forward_grouped: X", X, (T, D), _BF16)
+        _want("ffn_sparse_forward_grouped: W1", W1, (E, F, D), _BF16)
+        _want("ffn_sparse_forward_grouped: W2", W2, (E, D, F), _BF16)
+        _want("ffn_sparse_forward_grouped: b1", b1, (E, F), _F32, optional=True)
+        _check(load().ffn_sparse_forward_grouped(ctypes.byref(_cfg_with(self.cfg, weights_packed)), self.E, self.seg_c, _ptr(X), _ptr(W1), _ptr(W2),
+                                                 _ptr(b1), _ptr(self.Y3), _ptr(self.ws), self.layout["total"], _stream()))
+        return self.Y3
+
+    def backward(self, W1, dY):
+        """Alg. 2 alone for every expert (ffn_sparse_backward_grouped) on what the last forward() left."""
+        T, D, F, E = self.T, self.D, self.F, self.E
+        _want("ffn_sparse_backward_grouped: W1", W1, (E, F, D), _BF16)
+        _want("ffn_sparse_backward_grouped: dY", dY, (T, D), _BF16)
+        _check(load().ffn_sparse_backward_grouped(ctypes.byref(self.cfg), self.E, self.seg_c, _ptr(W1), _ptr(dY), _ptr(self.dX), _ptr(self.dW1),
+                                                  _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _stream()))
+        return self.dX, self.dW1, self.dW2
 
     def saved(self):
         """As FfnStep.saved(); weight-shaped tensors carry a leading expert axis."""
@@ -569,6 +618,24 @@ class FfnStepFp8:
                                           _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _ptr(self.amax), _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
 
+    def forward(self, X, W1, W2, b1, weights_packed=False):
+        """Alg. 1 alone (ffn_sparse_forward_fp8): Y3; amax[0:4] (x, w1, w2, y2) are written, what the backward pass needs stays in the workspace."""
+        T, D, F = self.T, self.D, self.F
+        _want("ffn_sparse_forward_fp8: X", X, (T, D), _BF16)
+        _want("ffn_sparse_forward_fp8: W1", W1, (F, D), _BF16)
+        _want("ffn_sparse_forward_fp8: W2", W2, (D, F), _BF16)
+        _want("ffn_sparse_forward_fp8: b1", b1, (F,), _F32, optional=True)
+        _check(load().ffn_sparse_forward_fp8(ctypes.byref(_cfg_with(self.cfg, weights_packed)), ctypes.byref(self.scales), _ptr(X), _ptr(W1), _ptr(W2),
+                                             _ptr(b1), _ptr(self.Y3), _ptr(self.ws), self.layout["total"], _ptr(self.amax), _stream()))
+        return self.Y3
+
+    def backward(self, dY):
+        """Alg. 2 alone (ffn_sparse_backward_fp8) on what the last forward() left (W1 is read as the codes that call wrote); amax[4:6] are written."""
+        _want("ffn_sparse_backward_fp8: dY", dY, (self.T, self.D), _BF16)
+        _check(load().ffn_sparse_backward_fp8(ctypes.byref(self.cfg), ctypes.byref(self.scales), _ptr(dY), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2),
+                                              _ptr(self.ws), self.layout["total"], _ptr(self.amax), _stream()))
+        return self.dX, self.dW1, self.dW2
+
     def saved(self):
         """Views of what the step leaves in its workspace."""
         T, D, F, L, M = self.T, self.D, self.F, self.layout, self.M
@@ -623,6 +690,25 @@ class FfnStepFp8Grouped(FfnStepFp8):
                                                   _ptr(b1), _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws),
                                                   self.layout["total"], _ptr(self.amax), _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
+
+    def forward(self, X, W1, W2, b1, weights_packed=False):
+        """Alg. 1 alone for every expert (ffn_sparse_forward_fp8_grouped); amax[0:4] are written."""
+        T, D, F, E = self.T, self.D, self.F, self.E
+        _want("ffn_sparse_forward_fp8_grouped: X", X, (T, D), _BF16)
+        _want("ffn_sparse_forward_fp8_grouped: W1", W1, (E, F, D), _BF16)
+        _want("ffn_sparse_forward_fp8_grouped: W2", W2, (E, D, F), _BF16)
+        _want("ffn_sparse_forward_fp8_grouped: b1", b1, (E, F), _F32, optional=True)
+        _check(load().ffn_sparse_forward_fp8_grouped(ctypes.byref(_cfg_with(self.cfg, weights_packed)), ctypes.byref(self.scales), self.E, self.seg_c,
+                                                     _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(self.Y3), _ptr(self.ws), self.layout["total"],
+                                                     _ptr(self.amax), _stream()))
+        return self.Y3
+
+    def backward(self, dY):
+        """Alg. 2 alone for every expert (ffn_sparse_backward_fp8_grouped) on what the last forward() left; amax[4:6] are written."""
+        _want("ffn_sparse_backward_fp8_grouped: dY", dY, (self.T, self.D), _BF16)
+        _check(load().ffn_sparse_backward_fp8_grouped(ctypes.byref(self.cfg), ctypes.byref(self.scales), self.E, self.seg_c, _ptr(dY), _ptr(self.dX),
+                                                      _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _ptr(self.amax), _stream()))
+        return self.dX, self.dW1, self.dW2
 
     def saved(self):
         """As FfnStepFp8.saved(); weight-shaped tensors carry a leading expert axis."""

@@ -450,7 +450,9 @@ bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L, int n_experts = 1) {
 
 int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, const int64_t* seg, const uint16_t* X, const uint16_t* W1,
                  const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace,
-                 size_t ws_bytes, float* amax, void* stream) {
+                 size_t ws_bytes, float* amax, void* stream, int phase = 3) {
+    // phase: bit 0 = Alg. 1 (forward pass), bit 1 = Alg. 2 (backward pass); a split call's halves meet through the workspace
+    const bool fwd = (phase & 1) != 0, bwd = (phase & 2) != 0;
     REQUIRE(cfg != nullptr && sc != nullptr, SFFN_EINVAL, "ffn_sparse_step_fp8: cfg or scales is null");
     REQUIRE(aligned16(amax), SFFN_EINVAL, "ffn_sparse_step_fp8: amax must be 16-byte aligned");
     Fp8Layout L;
@@ -460,7 +462,7 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
             "ffn_sparse_step_fp8: T must be a positive multiple of 64, D and F of 128 (M >= 16: 4 F / M a multiple of 128); flags: "
             "SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD, SFFN_FLAG_LEAN, SFFN_FLAG_WEIGHTS_PACKED");
     REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_sparse_step_fp8: unknown mode");
-    REQUIRE(X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_sparse_step_fp8: null pointer");
+    REQUIRE((!fwd || (X && W1 && W2 && Y3)) && (!bwd || (dY && dX && dW1 && dW2)), SFFN_EINVAL, "ffn_sparse_step_fp8: null pointer");
     REQUIRE(aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(dY) && aligned16(Y3) && aligned16(dX) && aligned16(dW1) && aligned16(dW2) &&
             aligned16(b1) && aligned16(workspace), SFFN_EINVAL, "ffn_sparse_step_fp8: pointers must be 16-byte aligned");
     REQUIRE(scale_ok(sc->x) && scale_ok(sc->w1) && scale_ok(sc->w2) && scale_ok(sc->y2) && scale_ok(sc->dy) && scale_ok(sc->dy1), SFFN_EINVAL,
@@ -507,7 +509,9 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     auto slot_of = [&](int i) { return slots ? slots + (size_t)i * 64 * 64 : nullptr; };
     float *ax = slot_of(0), *aw1 = slot_of(1), *aw2 = slot_of(2), *ay2 = slot_of(3), *ady = slot_of(4), *ady1 = slot_of(5);
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
-    if (amax) STAGE(launch_amax_clear(slots, 6, s), "step/clear(amax)");
+    // amax: the forward pass owns tensors 0-3 (x, w1, w2, y2), the backward pass 4-5 (dy, dy1); a split call clears and folds only its own
+    const int a_first = fwd ? 0 : 4, a_count = (bwd ? 6 : 4) - a_first;
+    if (amax) STAGE(launch_amax_clear(slot_of(a_first), a_count, s), "step/clear(amax)");
     // One data flow for every block width.  M = 8: the epilogues of eqs. (1), (4) also write the survivors' codes in the units of the V:2:8
     // activation GEMM (gemm_vnm8.hip), which picks the kept rows of the quantised W2.T / W1 while it reads its fragments.  M = 16, 32, 64
     // (Table 5): the general-M epilogues; eqs. (3), (7) fetch only the kept rows (gemm_gather.hip) and read the canonical codes.
@@ -520,50 +524,58 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     g_rows.role = 0; g_rows.b_stride = F * D;
     const GemmGroup* gr = g.n ? &g_rows : nullptr;
     // ---- Alg. 1 -------------------------------------------------------------------------------
-    if (w8) {       // X.T codes for eq. (8) and X codes for eq. (1) in one pass over X
+    if (fwd && w8) {       // X.T codes for eq. (8) and X codes for eq. (1) in one pass over X
         STAGE(launch_transpose_quantize_fp8_blocked(X, T, D, D, ix, (uint8_t*)xtb, s, ax, xq), "step/quantize(X, X.T)");
-    } else {
+    } else if (fwd) {
         STAGE(launch_transpose(X, T, D, D, xtb, 1, nullptr, s), "step/X.T");                                // bf16, for eq. (8)
         STAGE(launch_quantize_fp8_blocked(X, T, D, D, ix, xq, s, ax), "step/quantize(X)");
     }
     // W1 in one pass per expert: pruned (canonical + blocked codes) for eq. (1), and the un-pruned W1 as codes for eq. (7)
     const bool packed = (cfg->flags & SFFN_FLAG_WEIGHTS_PACKED) != 0;    // both weight passes skipped: the previous call's codes are still in the workspace
-    for (int64_t e = 0; e < E && !packed; ++e)
+    for (int64_t e = 0; e < E && fwd && !packed; ++e)
         STAGE(launch_prune24_fp8_step(W1 + e * F * D, F, D, D, 0, cfg->mode, iw1, w1c ? w1c + e * F * D / 2 : nullptr, w1m ? w1m + e * F * D / 8 : nullptr,
                                       w1b + e * F * D / 2, w1mb + e * F * D / 8, s, aw1, w1q + e * F * D), "step/prune24_fp8(W1)+quantize(W1)");
-    {   // eq. (1) on codes, then eq. (2) + V:N:M compression on the bf16 tile; the survivors leave as codes (and in bf16 for eq. (5))
+    if (fwd) {   // eq. (1) on codes, then eq. (2) + V:N:M compression on the bf16 tile; the survivors leave as codes (and in bf16 for eq. (5))
         VnmEpilogue ep;
         ep.mode = wide ? 5 : 1; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = (uint16_t*)y2c; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask;
         ep.ykept = ykept; ep.at = atb; ep.inv_out = 1.0f / sc->y2; ep.at_fp8 = w8; ep.amax = ay2;
         if (!wide) { ep.vcb = (uint16_t*)vcb; ep.mcb = mcb; ep.cixt = cixt; }
         STAGE(launch_gemm_fp8_blocked(w1b, w1mb, xq, b1, sc->x * sc->w1, F, T, D, y1, F, &ep, s, gp), "step/y1+sqrelu_vnm_compress");
     }
-    for (int64_t e = 0; e < E && !packed; ++e)
+    for (int64_t e = 0; e < E && fwd && !packed; ++e)
         STAGE(launch_prune24_fp8_step(W2 + e * D * F, F, D, F, 1, cfg->mode, iw2, w2c ? w2c + e * F * D / 2 : nullptr, w2m ? w2m + e * F * D / 8 : nullptr,
                                       w2b + e * F * D / 2, w2mb + e * F * D / 8, s, aw2, w2tq + e * F * D), "step/prune24_fp8(W2.T)+quantize(W2.T)");
-    if (wide) STAGE(launch_vnm_spmm_gather_fp8(y2c, y2m, cix, w2tq, D, sc->y2 * sc->w2, T, D, F, M, Y3, D, s, gr), "step/y3");      // eq. (3)
-    else      STAGE(launch_vnm8_gemm_fp8(vcb, mcb, cixt, w2tq, D, sc->y2 * sc->w2, T, D, F, Y3, D, s, gr), "step/y3");
+    if (fwd) {
+        if (wide) STAGE(launch_vnm_spmm_gather_fp8(y2c, y2m, cix, w2tq, D, sc->y2 * sc->w2, T, D, F, M, Y3, D, s, gr), "step/y3");      // eq. (3)
+        else STAGE(launch_vnm8_gemm_fp8(vcb, mcb, cixt, w2tq, D, sc->y2 * sc->w2, T, D, F, Y3, D, s, gr), "step/y3");
+    }
     // ---- Alg. 2 -------------------------------------------------------------------------------
-    if (w8) {
+    if (bwd && w8) {
         STAGE(launch_transpose_quantize_fp8_blocked(dY, T, D, D, idy, (uint8_t*)dytb, s, ady, dyq), "step/quantize(dY, dY.T)");
-    } else {
+    } else if (bwd) {
         STAGE(launch_transpose(dY, T, D, D, dytb, 1, nullptr, s), "step/dY.T");                             // bf16, for eq. (5)
         STAGE(launch_quantize_fp8_blocked(dY, T, D, D, idy, dyq, s, ady), "step/quantize(dY)");
     }
-    if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)dytb, sc->y2 * sc->dy, F, D, T, 1, dW2, F, s, gw), "step/dW2");   // eq. (5) on codes
-    else    STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");               // eq. (5), bf16
-    {   // eq. (4) on codes, then eq. (6) in bf16 on y2's kept slots; dy1 leaves as codes (eq. (7)) and, at M = 8, in bf16 (canonical)
+    if (bwd) {
+        if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)dytb, sc->y2 * sc->dy, F, D, T, 1, dW2, F, s, gw), "step/dW2");   // eq. (5) on codes
+        else STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");               // eq. (5), bf16
+    }
+    if (bwd) {   // eq. (4) on codes, then eq. (6) in bf16 on y2's kept slots; dy1 leaves as codes (eq. (7)) and, at M = 8, in bf16 (canonical)
         VnmEpilogue ep;
         ep.mode = wide ? 6 : 2; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = wide ? (uint16_t*)dy1c : dy1v; ep.meta = y2m; ep.colidx = cix;
         ep.ykept = ykept; ep.at = atb; ep.inv_out = 1.0f / sc->dy1; ep.at_fp8 = w8; ep.amax = ady1;
         if (!wide) ep.vcb = (uint16_t*)vcb;
         STAGE(launch_gemm_fp8_blocked(w2b, w2mb, dyq, nullptr, sc->dy * sc->w2, F, T, D, dy2, F, &ep, s, gp), "step/dy2+dsqrelu_vnm");
     }
-    if (wide) STAGE(launch_vnm_spmm_gather_fp8(dy1c, y2m, cix, w1q, D, sc->dy1 * sc->w1, T, D, F, M, dX, D, s, gr), "step/dX");     // eq. (7)
-    else      STAGE(launch_vnm8_gemm_fp8(vcb, mcb, cixt, w1q, D, sc->dy1 * sc->w1, T, D, F, dX, D, s, gr), "step/dX");
-    if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)xtb, sc->dy1 * sc->x, F, D, T, 0, dW1, D, s, gw), "step/dW1");   // eq. (8) on codes
-    else    STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                // eq. (8), bf16
-    if (amax) STAGE(launch_amax_finish(slots, 6, amax, s), "step/finish(amax)");
+    if (bwd) {
+        if (wide) STAGE(launch_vnm_spmm_gather_fp8(dy1c, y2m, cix, w1q, D, sc->dy1 * sc->w1, T, D, F, M, dX, D, s, gr), "step/dX");     // eq. (7)
+        else STAGE(launch_vnm8_gemm_fp8(vcb, mcb, cixt, w1q, D, sc->dy1 * sc->w1, T, D, F, dX, D, s, gr), "step/dX");
+    }
+    if (bwd) {
+        if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)xtb, sc->dy1 * sc->x, F, D, T, 0, dW1, D, s, gw), "step/dW1");   // eq. (8) on codes
+        else STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                // eq. (8), bf16
+    }
+    if (amax) STAGE(launch_amax_finish(slot_of(a_first), a_count, amax + a_first, s), "step/finish(amax)");
     return SFFN_OK;
 }
 }  // namespace
@@ -601,6 +613,27 @@ int ffn_sparse_step_fp8_grouped(const sffn_cfg* cfg, const sffn_fp8_scales* sc, 
                                 uint16_t* dW2, void* workspace, size_t ws_bytes, float* amax, void* stream) {
     REQUIRE(seg_offsets != nullptr, SFFN_EINVAL, "ffn_sparse_step_fp8_grouped: seg_offsets is null");
     return run_fp8_step(cfg, sc, n_experts, seg_offsets, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, ws_bytes, amax, stream);
+}
+
+// Alg. 1 / Alg. 2 as separate calls (other layers run between a layer's forward and backward pass); the halves meet through the workspace
+int ffn_sparse_forward_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* sc, const uint16_t* X, const uint16_t* W1, const uint16_t* W2, const float* b1,
+                           uint16_t* Y3, void* workspace, size_t ws_bytes, float* amax, void* stream) {
+    return run_fp8_step(cfg, sc, 1, nullptr, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, workspace, ws_bytes, amax, stream, 1);
+}
+int ffn_sparse_backward_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* sc, const uint16_t* dY, uint16_t* dX, uint16_t* dW1, uint16_t* dW2,
+                            void* workspace, size_t ws_bytes, float* amax, void* stream) {
+    return run_fp8_step(cfg, sc, 1, nullptr, nullptr, nullptr, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, amax, stream, 2);
+}
+int ffn_sparse_forward_fp8_grouped(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, const int64_t* seg_offsets, const uint16_t* X,
+                                   const uint16_t* W1, const uint16_t* W2, const float* b1, uint16_t* Y3, void* workspace, size_t ws_bytes, float* amax,
+                                   void* stream) {
+    REQUIRE(seg_offsets != nullptr, SFFN_EINVAL, "ffn_sparse_forward_fp8_grouped: seg_offsets is null");
+    return run_fp8_step(cfg, sc, n_experts, seg_offsets, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, workspace, ws_bytes, amax, stream, 1);
+}
+int ffn_sparse_backward_fp8_grouped(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, const int64_t* seg_offsets, const uint16_t* dY,
+                                    uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, float* amax, void* stream) {
+    REQUIRE(seg_offsets != nullptr, SFFN_EINVAL, "ffn_sparse_backward_fp8_grouped: seg_offsets is null");
+    return run_fp8_step(cfg, sc, n_experts, seg_offsets, nullptr, nullptr, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, amax, stream, 2);
 }
 
 // ---- Section 3.3 / Alg. 3: neuron-level experts that emit the V:N:M format ----------------------------------------
@@ -883,8 +916,10 @@ int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint1
 // the plain step).  Every stage is one launch; the GEMMs find their expert from the segment table.
 static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, const uint16_t* X, const uint16_t* W1,
                     const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
-                    uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
-    REQUIRE(cfg && X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_sparse_step: null pointer");
+                    uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream, int phase = 3) {
+    // phase: bit 0 = Alg. 1 (forward pass), bit 1 = Alg. 2 (backward pass); the two halves of a split call meet through the workspace
+    const bool fwd = (phase & 1) != 0, bwd = (phase & 2) != 0;
+    REQUIRE(cfg && W1 && (!fwd || (X && W2 && Y3)) && (!bwd || (dY && dX && dW1 && dW2)), SFFN_EINVAL, "ffn_sparse_step: null pointer");
     FullLayout L;
     REQUIRE(n_experts >= 1 && n_experts <= GemmGroup::kMaxExperts, SFFN_EINVAL, "ffn_sparse_step_grouped: n_experts must be in 1..64");
     REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "ffn_sparse_step: only V=64 with M in {8, 16, 32, 64} is built");
@@ -934,6 +969,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     // the conversion is paid once per optimizer step, not once per micro-batch)
     const bool packed = (cfg->flags & SFFN_FLAG_WEIGHTS_PACKED) != 0;
     REQUIRE(!packed || cfg->M == 8 || fused_wide(cfg), SFFN_EUNSUPPORTED, "ffn_sparse_step: SFFN_FLAG_WEIGHTS_PACKED is not built for the unfused path");
+    REQUIRE(phase == 3 || cfg->M == 8 || fused_wide(cfg), SFFN_EUNSUPPORTED, "ffn_sparse_forward / ffn_sparse_backward: not built for the unfused path");
     if (fused_wide(cfg)) {
         // Blocks of M = 16, 32, 64 columns (Table 5), fused like the M = 8 step: eq. (2) + compression in the epilogue of eq. (1), eq. (6)
         // in the epilogue of eq. (4) (the dense y1 / dy2 stay in LDS), eqs. (3), (7) on the kept rows of W2.T / W1 only (the pruning
@@ -949,25 +985,25 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
         const GemmGroup* gw = g.n ? &g_wgrad : nullptr;
         uint16_t* w2t = w1tb;                            // W2.T [F, D] per expert
         if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
-        STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
         const bool lean_w = (cfg->flags & SFFN_FLAG_LEAN) != 0;        // no canonical copies of the packed weights (the packed activations stay: eqs. (3), (7) read them)
-        if (!packed) STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, lean_w ? nullptr : w1v, lean_w ? nullptr : w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
-        {
+        if (fwd) STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
+        if (fwd && !packed) STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, lean_w ? nullptr : w1v, lean_w ? nullptr : w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
+        if (fwd) {
             VnmEpilogue ep;
             ep.mode = 5; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = y2v; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept; ep.at = atb;
             STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s, gp), "step/y1+sqrelu_vnm_compress");         // eqs. (1), (2), Section 2.3
         }
-        if (!packed) STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, lean_w ? nullptr : w2v, lean_w ? nullptr : w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
-        STAGE(launch_vnm_spmm_gather(y2v, y2m, cix, w2t, D, T, D, F, M, Y3, D, s, gr), "step/y3");                              // eq. (3)
-        STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
-        STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");                                       // eq. (5)
-        {
+        if (fwd && !packed) STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, lean_w ? nullptr : w2v, lean_w ? nullptr : w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
+        if (fwd) STAGE(launch_vnm_spmm_gather(y2v, y2m, cix, w2t, D, T, D, F, M, Y3, D, s, gr), "step/y3");                              // eq. (3)
+        if (bwd) STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
+        if (bwd) STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");                                       // eq. (5)
+        if (bwd) {
             VnmEpilogue ep;
             ep.mode = 6; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept; ep.at = atb;
             STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, ep, s, gp), "step/dy2+dsqrelu_vnm");         // eqs. (4), (6)
         }
-        STAGE(launch_vnm_spmm_gather(dy1v, y2m, cix, W1, D, T, D, F, M, dX, D, s, gr), "step/dX");                              // eq. (7), dense W1 as is
-        STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                                        // eq. (8)
+        if (bwd) STAGE(launch_vnm_spmm_gather(dy1v, y2m, cix, W1, D, T, D, F, M, dX, D, s, gr), "step/dX");                              // eq. (7), dense W1 as is
+        if (bwd) STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                                        // eq. (8)
         return SFFN_OK;
     }
     if (cfg->M != 8) {
@@ -1039,28 +1075,28 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     uint8_t* cixt = a24m + up256((size_t)T * F / 16);
     uint16_t* w2t = w2b;                                         // W2.T [F, D] per expert
     g_dense.b_stride = F * D;
-    STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
+    if (fwd) STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
     // row pruning is per row, so the E stacked [F, D] matrices are one [E * F, D] matrix
-    if (!packed) STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, lean ? nullptr : w1v, lean ? nullptr : w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
-    {   // eq. (1), then eq. (2) + V:N:M compression on the tile while it is still in LDS
+    if (fwd && !packed) STAGE(launch_prune24_step(W1, E * F, D, D, 0, cfg->mode, lean ? nullptr : w1v, lean ? nullptr : w1m, w1vb, w1mb, nullptr, s), "step/prune24(W1)");
+    if (fwd) {   // eq. (1), then eq. (2) + V:N:M compression on the tile while it is still in LDS
         VnmEpilogue ep;
         ep.mode = 1; ep.store_dense = keep_dense; ep.vals = lean ? nullptr : y2v; ep.meta = y2m; ep.colidx = cix; ep.kmask = kmask; ep.ykept = ykept;
         ep.vcb = vcb; ep.mcb = mcb; ep.cixt = cixt; ep.at = atb;
         STAGE(launch_gemm_vnm_epilogue(w1vb, w1mb, xb, b1, F, T, D, y1, ep, s, gp), "step/y1+sqrelu_vnm_compress");
     }
-    if (!packed) STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, lean ? nullptr : w2v, lean ? nullptr : w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
-    STAGE(launch_vnm8_gemm(vcb, mcb, cixt, w2t, D, T, D, F, Y3, D, s, gd), "step/y3");                         // eq. (3)
+    if (fwd && !packed) STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, lean ? nullptr : w2v, lean ? nullptr : w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
+    if (fwd) STAGE(launch_vnm8_gemm(vcb, mcb, cixt, w2t, D, T, D, F, Y3, D, s, gd), "step/y3");                         // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
-    STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
-    STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");                          // eq. (5)
-    {   // eq. (4), then eq. (6) on y2's kept slots; overwrites the survivors and the transposed tile with dy1's
+    if (bwd) STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
+    if (bwd) STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");                          // eq. (5)
+    if (bwd) {   // eq. (4), then eq. (6) on y2's kept slots; overwrites the survivors and the transposed tile with dy1's
         VnmEpilogue ep;
         ep.mode = 2; ep.store_dense = keep_dense; ep.vals = lean ? nullptr : dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
         ep.vcb = vcb; ep.at = atb;
         STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, ep, s, gp), "step/dy2+dsqrelu_vnm");
     }
-    STAGE(launch_vnm8_gemm(vcb, mcb, cixt, W1, D, T, D, F, dX, D, s, gd), "step/dX");                          // eq. (7), dense W1 as is
-    STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                           // eq. (8)
+    if (bwd) STAGE(launch_vnm8_gemm(vcb, mcb, cixt, W1, D, T, D, F, dX, D, s, gd), "step/dX");                          // eq. (7), dense W1 as is
+    if (bwd) STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                           // eq. (8)
     (void)w1tb;
     return SFFN_OK;
 }
@@ -1069,6 +1105,26 @@ int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, 
                     const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace,
                     size_t ws_bytes, void* stream) {
     return run_step(cfg, 1, nullptr, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, ws_bytes, stream);
+}
+
+// Alg. 1 / Alg. 2 as separate calls (other layers run between a layer's forward and backward pass); the halves meet through the workspace
+int ffn_sparse_forward(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, const uint16_t* W2, const float* b1, uint16_t* Y3,
+                       void* workspace, size_t ws_bytes, void* stream) {
+    return run_step(cfg, 1, nullptr, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, workspace, ws_bytes, stream, 1);
+}
+int ffn_sparse_backward(const sffn_cfg* cfg, const uint16_t* W1, const uint16_t* dY, uint16_t* dX, uint16_t* dW1, uint16_t* dW2,
+                        void* workspace, size_t ws_bytes, void* stream) {
+    return run_step(cfg, 1, nullptr, nullptr, W1, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, stream, 2);
+}
+int ffn_sparse_forward_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* seg_offsets, const uint16_t* X, const uint16_t* W1,
+                               const uint16_t* W2, const float* b1, uint16_t* Y3, void* workspace, size_t ws_bytes, void* stream) {
+    REQUIRE(seg_offsets != nullptr, SFFN_EINVAL, "ffn_sparse_forward_grouped: seg_offsets is null");
+    return run_step(cfg, n_experts, seg_offsets, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, workspace, ws_bytes, stream, 1);
+}
+int ffn_sparse_backward_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* seg_offsets, const uint16_t* W1, const uint16_t* dY,
+                                uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
+    REQUIRE(seg_offsets != nullptr, SFFN_EINVAL, "ffn_sparse_backward_grouped: seg_offsets is null");
+    return run_step(cfg, n_experts, seg_offsets, nullptr, W1, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, stream, 2);
 }
 
 size_t sffn_grouped_workspace_bytes(const sffn_cfg* cfg, int n_experts) {

@@ -72,6 +72,14 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     huge = binding._Cfg(64, 32768, 65536, 64, 8, 0, 0)                    # a 4 GiB weight matrix: beyond the 32-bit offsets of the V:2:8 kernel's loads
     assert lib.ffn_sparse_step(ctypes.byref(huge), *args, fake, 1 << 50, None) == -2
     assert lib.ffn_sparse_step(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 8, 0, 64)), *args, fake, 1 << 40, None) == -1        # unknown flag
+    # Alg. 1 / Alg. 2 as separate calls: each half checks its own pointers, the workspace and the path before any launch
+    assert lib.ffn_sparse_forward(ctypes.byref(cfg), fake, fake, fake, fake, fake, fake, 16, None) == -3
+    assert lib.ffn_sparse_forward(ctypes.byref(cfg), None, fake, fake, fake, fake, fake, 1 << 40, None) == -1
+    assert lib.ffn_sparse_backward(ctypes.byref(cfg), fake, fake, fake, fake, fake, fake, 16, None) == -3
+    assert lib.ffn_sparse_backward(ctypes.byref(cfg), fake, None, fake, fake, fake, fake, 1 << 40, None) == -1
+    assert lib.ffn_sparse_backward(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 16, 0, 2)), fake, fake, fake, fake, fake, fake, 1 << 40, None) == -2   # unfused path
+    assert lib.ffn_sparse_forward_grouped(ctypes.byref(cfg), 2, None, fake, fake, fake, fake, fake, fake, 1 << 40, None) == -1
+    assert lib.ffn_sparse_backward_grouped(ctypes.byref(cfg), 2, None, fake, fake, fake, fake, fake, fake, 1 << 40, None) == -1
     # SFFN_FLAG_WEIGHTS_PACKED (16) exists for the fused paths only: the unfused wide-block path (flag 2) refuses it before any launch
     assert lib.ffn_sparse_step(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 16, 0, 2 | 16)), *args, fake, 1 << 40, None) == -2
     # the fp8 step: scales are a host struct; shapes, flags, scales and the workspace are checked before anything is enqueued
@@ -83,6 +91,12 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     assert lib.ffn_sparse_step_fp8(ctypes.byref(binding._Cfg(512, 256, 1280, 64, 64, 0, 0)), ctypes.byref(sc), *args, fake, 1 << 40, None, None) == -1  # 4 F / M = 80
     assert lib.ffn_sparse_step_fp8(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 16, 0, 0)), ctypes.byref(sc), *args, fake, 16, None, None) == -3       # M = 16: workspace
     assert lib.ffn_sparse_step_fp8(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 8, 0, 2)), ctypes.byref(sc), *args, fake, 1 << 40, None, None) == -1   # unknown flag
+    assert lib.ffn_sparse_forward_fp8(ctypes.byref(cfg), ctypes.byref(sc), None, fake, fake, fake, fake, fake, 1 << 40, None, None) == -1
+    assert lib.ffn_sparse_forward_fp8(ctypes.byref(cfg), ctypes.byref(sc), fake, fake, fake, fake, fake, fake, 16, None, None) == -3
+    assert lib.ffn_sparse_backward_fp8(ctypes.byref(cfg), ctypes.byref(sc), fake, fake, fake, None, fake, 1 << 40, None, None) == -1
+    assert lib.ffn_sparse_backward_fp8(ctypes.byref(cfg), ctypes.byref(sc), fake, fake, fake, fake, fake, 16, None, None) == -3
+    assert lib.ffn_sparse_forward_fp8_grouped(ctypes.byref(cfg), ctypes.byref(sc), 2, None, fake, fake, fake, fake, fake, fake, 1 << 40, None, None) == -1
+    assert lib.ffn_sparse_backward_fp8_grouped(ctypes.byref(cfg), ctypes.byref(sc), 2, None, fake, fake, fake, fake, fake, 1 << 40, None, None) == -1
     zero = binding._Fp8Scales(1.0, 1.0, 0.0, 1.0, 1.0, 1.0)
     assert lib.ffn_sparse_step_fp8(ctypes.byref(cfg), ctypes.byref(zero), *args, fake, 1 << 40, None, None) == -1 and b"scales" in lib.sffn_last_error()
     assert lib.sffn_fp8_workspace_bytes(ctypes.byref(cfg)) > 0 and lib.sffn_fp8_workspace_bytes(ctypes.byref(binding._Cfg(512, 192, 1024, 64, 8, 0, 0))) == 0

@@ -391,6 +391,42 @@ def test_fp8_step_on_packed_weights_is_bit_identical(M, wgrad_fp8, lean):
         assert ga[k] == wa[k], k
 
 
+@pytest.mark.parametrize("M,wgrad_fp8", [(8, False), (8, True), (32, True)])
+def test_fp8_forward_and_backward_as_separate_calls_are_bit_identical(M, wgrad_fp8):
+    """ffn_sparse_forward_fp8 + ffn_sparse_backward_fp8 against the one-call fp8 step: outputs and the six maxima (the forward call owns
+    x, w1, w2, y2, the backward call dy, dy1)."""
+    T, D, F = 320, 256, 1024
+    inp = make_ffn_inputs(T, D, F, seed=51)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    sc = dict(x=5.0 / 448, w1=0.1 / 448, w2=0.1 / 448, y2=8.0 / 448, dy=5.0 / 448, dy1=2.0 / 448)
+    split = sffn.FfnStepFp8(T, D, F, sc, sffn.MODE_HARD, wgrad_fp8=wgrad_fp8, M=M)
+    whole = sffn.FfnStepFp8(T, D, F, sc, sffn.MODE_HARD, wgrad_fp8=wgrad_fp8, M=M)
+    split.amax.fill_(-1.0)
+    y3 = to_bits(split.forward(dev["X"], dev["W1"], dev["W2"], dev["b1"])).copy()
+    mid = split.amax_dict()
+    assert mid["dy"] == -1.0 and mid["dy1"] == -1.0 and mid["x"] > 0 and mid["y2"] > 0       # the forward call leaves the backward pass's maxima alone
+    want = [to_bits(t).copy() for t in whole(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    got = [y3] + [to_bits(t).copy() for t in split.backward(dev["dY"])]
+    for name, x, y in zip(("Y3", "dX", "dW1", "dW2"), got, want):
+        assert np.array_equal(x, y), name
+    assert split.amax_dict() == whole.amax_dict()
+
+
+def test_fp8_grouped_forward_and_backward_as_separate_calls_are_bit_identical():
+    from workload import make_moe_inputs
+    D, F = 256, 384
+    m = make_moe_inputs(n_tokens=700, n_experts=3, top_k=2, D=D, F=F, seed=6)
+    dev = {k: to_dev(m[k]) for k in ("X", "W1", "W2", "b1", "dY")}
+    sc = dict(x=5.0 / 448, w1=0.1 / 448, w2=0.1 / 448, y2=8.0 / 448, dy=5.0 / 448, dy1=2.0 / 448)
+    split, whole = sffn.FfnStepFp8Grouped(m["seg"], D, F, sc, wgrad_fp8=True), sffn.FfnStepFp8Grouped(m["seg"], D, F, sc, wgrad_fp8=True)
+    y3 = to_bits(split.forward(dev["X"], dev["W1"], dev["W2"], dev["b1"])).copy()
+    want = [to_bits(t).copy() for t in whole(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    got = [y3] + [to_bits(t).copy() for t in split.backward(dev["dY"])]
+    for name, x, y in zip(("Y3", "dX", "dW1", "dW2"), got, want):
+        assert np.array_equal(x, y), name
+    assert split.amax_dict() == whole.amax_dict()
+
+
 @pytest.mark.parametrize("wgrad_fp8", [False, True])
 def test_grouped_fp8_step_matches_oracle_per_expert(wgrad_fp8):
     """The mixture-of-experts form of the fp8 step (uneven segments, one of them empty): every expert's share is checked

@@ -731,6 +731,42 @@ def test_grouped_step_on_packed_weights_is_bit_identical():
         assert np.array_equal(x, y), name
 
 
+@pytest.mark.parametrize("M,lean", [(8, False), (8, True), (16, False), (64, True)])
+def test_forward_and_backward_as_separate_calls_are_bit_identical(M, lean):
+    """ffn_sparse_forward (Alg. 1) + ffn_sparse_backward (Alg. 2) against the one-call step; two layers' forward passes run before their backward
+    passes, in the order a training loop has them, so nothing may hide in library state outside each layer's workspace."""
+    T, D, F = 320, 256, 1024
+    layers = [make_ffn_inputs(T, D, F, seed=41 + i) for i in range(2)]
+    dev = [{k: to_dev(v) for k, v in inp.items()} for inp in layers]
+    split = [sffn.FfnStep(T, D, F, sffn.MODE_SOFT, M=M, lean=lean) for _ in layers]
+    y3 = [to_bits(st.forward(d["X"], d["W1"], d["W2"], d["b1"])).copy() for st, d in zip(split, dev)]
+    grads = [None, None]
+    for i in (1, 0):
+        grads[i] = [to_bits(t).copy() for t in split[i].backward(dev[i]["W1"], dev[i]["dY"])]
+    for i, d in enumerate(dev):
+        whole = sffn.FfnStep(T, D, F, sffn.MODE_SOFT, M=M, lean=lean)
+        want = [to_bits(t).copy() for t in whole(d["X"], d["W1"], d["W2"], d["b1"], d["dY"])]
+        assert np.array_equal(y3[i], want[0]), "Y3"
+        for name, x, y in zip(("dX", "dW1", "dW2"), grads[i], want[1:]):
+            assert np.array_equal(x, y), (i, name)
+        sa, sb = split[i].saved(), whole.saved()
+        for k in ("y2_meta", "colidx", "y1_kept") + (() if lean else ("y2_vals", "dy1_vals", "w2t_vals")):
+            assert np.array_equal(to_bits(sa[k]), to_bits(sb[k])), k
+
+
+def test_grouped_forward_and_backward_as_separate_calls_are_bit_identical():
+    D, F = 192, 320
+    m = make_moe_inputs(n_tokens=900, n_experts=4, top_k=2, D=D, F=F, seed=5)
+    dev = {k: to_dev(m[k]) for k in ("X", "W1", "W2", "b1", "dY")}
+    split, whole = sffn.FfnStepGrouped(m["seg"], D, F), sffn.FfnStepGrouped(m["seg"], D, F)
+    y3 = to_bits(split.forward(dev["X"], dev["W1"], dev["W2"], dev["b1"])).copy()
+    whole(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])                             # another layer's work in between
+    got = [y3] + [to_bits(t).copy() for t in split.backward(dev["W1"], dev["dY"])]
+    want = [to_bits(t).copy() for t in (whole.Y3, whole.dX, whole.dW1, whole.dW2)]
+    for name, x, y in zip(("Y3", "dX", "dW1", "dW2"), got, want):
+        assert np.array_equal(x, y), name
+
+
 def test_lean_grouped_step_is_bit_identical():
     D, F = 192, 320
     m = make_moe_inputs(n_tokens=900, n_experts=4, top_k=2, D=D, F=F, seed=2)
