@@ -44,6 +44,22 @@ def test_prune24_rows(R, K, mode):
     assert np.array_equal(to_bits(vals), rv)
 
 
+@pytest.mark.parametrize("trans", [False, True])
+def test_prune24_hard_on_every_bit_pattern(trans):
+    """HARD pruning is defined on bit patterns (magnitude = the pattern without its sign, compared as an integer), so it is total: infinities
+    and NaNs rank above every finite value and survive with their bits untouched.  Uniform random patterns put a non-finite entry into
+    about 3 % of the groups."""
+    R, K = 256, 512
+    rng = np.random.default_rng(17)
+    S = rng.integers(0, 1 << 16, (R, K), dtype=np.uint16)
+    S[0, :8] = [0x7F80, 0xFF80, 0x7FC0, 0x7F7F, 0xFFFF, 0x7F81, 0x7F80, 0x0000]      # inf, -inf, NaNs and the largest finite value side by side
+    stored = np.ascontiguousarray(S.T) if trans else S
+    vals, meta = sffn.prune24_compress(to_dev(stored), trans=trans, mode=sffn.MODE_HARD)
+    rv, rm = oracle.prune24_compress(S, sffn.MODE_HARD)
+    assert np.array_equal(to_bits(meta), rm)
+    assert np.array_equal(to_bits(vals), rv)
+
+
 def test_prune24_rows_strided():
     rng = np.random.default_rng(5)
     big = rnd_bits(rng, (128, 384), 0.02)
@@ -70,6 +86,37 @@ def test_prune24_trans(R, K, mode):
 
 def _y1_like(rng, T, F, shift=1.28):
     return bf16_bits_from_f32(rng.standard_normal((T, F), dtype=np.float32) - np.float32(shift))
+
+
+@pytest.mark.parametrize("M", [8, 16])
+def test_sqrelu_vnm_compress_with_infinite_activations(M):
+    """Overflow is part of bf16 training: +inf pre-activations, squares that overflow (max finite, 2^64) and -inf (ReLU: 0).  An infinite
+    column score outranks every finite one, two infinite columns of a block tie to the lower index, and the packed values carry +inf."""
+    T, F = 128, 512
+    rng = np.random.default_rng(3)
+    y1 = _y1_like(rng, T, F, 1.0)
+    y1[3, 5] = y1[7, 5] = y1[9, 6] = 0x7F80
+    y1[70, 100] = 0xFF80
+    y1[80, 200], y1[81, 201] = 0x7F7F, 0x5F80
+    v, m, c = sffn.sqrelu_vnm_compress(to_dev(y1), 64, M)
+    rv, rm, rc = oracle.sqrelu_vnm_compress(y1, 64, M)
+    assert np.array_equal(to_bits(c), rc) and np.array_equal(to_bits(m), rm) and np.array_equal(to_bits(v), rv)
+    assert (rv == 0x7F80).sum() >= 4
+
+
+def test_fused_step_with_an_infinite_bias_packs_like_the_oracle():
+    """The fused eq. (1) epilogue on a hidden unit whose pre-activation is +inf for every token (bias = inf)."""
+    T, D, F = 128, 128, 256
+    inp = make_ffn_inputs(T, D, F, seed=1)
+    inp["b1"][5] = np.float32(np.inf)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    st = sffn.FfnStep(T, D, F, sffn.MODE_HARD, keep_dense=True)
+    st(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    s = st.saved()
+    y1 = to_bits(s["y1"])
+    assert (y1[:, 5] == 0x7F80).all()
+    rv, rm, rc = oracle.sqrelu_vnm_compress(y1, 64, 8)
+    assert np.array_equal(to_bits(s["colidx"]), rc) and np.array_equal(to_bits(s["y2_meta"]), rm) and np.array_equal(to_bits(s["y2_vals"]), rv)
 
 
 @pytest.mark.parametrize("T,F", [(64, 64), (128, 512), (192, 1088), (512, 1024)])

@@ -127,3 +127,14 @@ def test_special_values_are_deterministic(mode):
     v2, m2 = oracle.prune24_compress(row.copy(), mode)
     assert np.array_equal(v1, v2) and np.array_equal(m1, m2)
     assert m1[0, 0] == ((0 | 3 << 2) | ((0 | 1 << 2) << 4))  # subnormals beat zeros; +-max beat +-1
+
+
+def test_hard_pruning_is_total_on_bit_patterns():
+    """Section 2.2 ranks magnitudes; read on bit patterns (sign cleared, compared as integers) the rule also orders what is not a number:
+    NaN patterns above infinity above every finite value, ties to the lower index, and HARD mode hands the survivors on untouched."""
+    row = np.array([[0x7F80, 0x3F80, 0x7FC1, 0x4000,          # inf, 1, NaN, 2        -> positions 0, 2
+                     0xFF80, 0x7F80, 0x7F7F, 0xFF7F]],         # -inf, inf, max, -max  -> the two infinities (tie: lower index first)
+                   dtype=np.uint16)
+    v, m = oracle.prune24_compress(row, HARD)
+    assert list(v[0]) == [0x7F80, 0x7FC1, 0xFF80, 0x7F80]
+    assert m[0, 0] == ((0 | 2 << 2) | ((0 | 1 << 2) << 4))
