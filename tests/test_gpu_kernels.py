@@ -314,6 +314,13 @@ def test_ffn_sparse_step_ragged_shape():
     _teacher_forced_step_check(192, 320, 448, sffn.MODE_SOFT, seed=3)
 
 
+@pytest.mark.parametrize("T,D,F", [(64, 64, 64), (65472, 64, 128)])
+def test_ffn_sparse_step_at_the_ends_of_the_size_range(T, D, F):
+    """The smallest shape the step accepts (one V:N:M block row, one tile, one stage of every ring) and the largest token count
+    (T below 65536: 1023 token blocks, 256 tile rows), stage by stage against the oracle."""
+    _teacher_forced_step_check(T, D, F, sffn.MODE_HARD, seed=9)
+
+
 def test_step_without_dense_intermediates_is_bit_identical():
     """The benchmarked configuration does not store the dense y1 / dy2; everything else it produces must be the
     same bits as the checked configuration that does."""
