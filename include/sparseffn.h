@@ -150,7 +150,7 @@ int spmm24_prepared(const uint16_t* X, const void* w_prepared, const float* bias
  * matrix (a_vals [T,Kfull/4], a_meta [T,Kfull/16], a_colidx [T/64,Kfull/8,4]) and W dense.
  * ldw = row stride of Wd in elements.  workspace: sffn_vnm_spmm_workspace_bytes() (the same size
  * for both orientations: scratch for the activation in the layout the kernel of the route reads and for a
- * transposed copy of Wd).  Routes: M = 8 (Wd below 4 GiB): the packed activation as it is on 256-token tiles, the
+ * transposed copy of Wd).  Routes: M = 8 (Wd below 2 GiB): the packed activation as it is on 256-token tiles, the
  * kept rows of the contraction-major W picked while the fragments are read; M >= 16 with 4*Kfull/M a multiple of 64
  * and at most 7168: only the kept rows of W are fetched (gathered per 64-token block); otherwise the activation
  * is contracted as a plain 2:4 matrix over all Kfull columns.  All routes compute the same sums (fp32 accumulation
@@ -302,6 +302,9 @@ int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint1
  * Y3 [T,D], dX [T,D], dW1 [F,D], dW2 [D,F]; intermediates land in `workspace` at the offsets of
  * sffn_workspace_layout().  Both weight matrices are re-pruned inside the call (SFFN_FLAG_WEIGHTS_PACKED: a later micro-batch
  * of the same optimizer step reuses what the previous call packed).
+ * Size limits (SFFN_EUNSUPPORTED beyond them, nothing enqueued): T below 65536; one weight matrix below 2 GiB (F * D below 2^30 elements;
+ * fp8 step: below 2^31), because the kernels of eqs. (3), (7) address the dense weight with 32-bit offsets (cfg->M = 16, 32, 64 in bf16:
+ * a larger weight takes the unfused path, which contracts the activation as plain 2:4 and has no such limit).
  * cfg->M = 16, 32 or 64 (Table 5): the same algorithm and the same fusion; eqs. (3), (7) contract only the kept rows of
  * W2.T / W1 (see vnm_spmm), and the packed activation tensors have the sizes given above.  Shapes whose 4 F / M is not a
  * multiple of 64 or exceeds 7168, and calls with SFFN_FLAG_UNFUSED, run eqs. (2), (6) as separate kernels instead: the dense

@@ -50,7 +50,7 @@ struct FullLayout {
 // Blocks of M = 16, 32, 64 columns take the fused path (V:N:M epilogues inside eqs. (1), (4), gathered-row eqs. (3), (7)) when the
 // gathered-row kernel covers the shape and the caller does not ask for the unfused reference path.
 bool fused_wide(const sffn_cfg* c) {
-    return c->M != 8 && !(c->flags & SFFN_FLAG_UNFUSED) && vnm_spmm_gather_ok(c->T, c->D, c->F, c->M) && c->F * c->D * 2 < ((int64_t)1 << 32);
+    return c->M != 8 && !(c->flags & SFFN_FLAG_UNFUSED) && vnm_spmm_gather_ok(c->T, c->D, c->F, c->M) && c->F * c->D * 2 < ((int64_t)1 << 31);
 }
 
 // E = number of experts (1 for the plain step): every weight-shaped tensor holds E matrices back to back.
@@ -245,7 +245,7 @@ int vnm_spmm(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* a_col
         LAUNCH(launch_vnm8_gemm(vcb, mcb, cixt, W, ldk, T, N, Kfull, out, N, s), "vnm_spmm/gemm");
         return SFFN_OK;
     }
-    if ((M >= 16 || w_kmajor) && vnm_spmm_gather_ok(T, N, Kfull, M) && Kfull * (w_kmajor ? ldw : N) * 2 < ((int64_t)1 << 32)) {
+    if ((M >= 16 || w_kmajor) && vnm_spmm_gather_ok(T, N, Kfull, M) && Kfull * (w_kmajor ? ldw : N) * 2 < ((int64_t)1 << 31)) {
         // contract over the 4 Kfull / M kept columns only, gathering their rows of the [Kfull, N] operand (M = 8: the two routes
         // are equally fast, so it is taken only when it saves the transpose of Wd)
         int64_t ldk = ldw;
@@ -396,7 +396,7 @@ int vnm_spmm_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* a
         LAUNCH(launch_vnm8_gemm_fp8(vcb, mcb, cixt, W, N, scale_a * scale_w, T, N, Kfull, out, N, s), "vnm_spmm_fp8/gemm");
         return SFFN_OK;
     }
-    if (M >= 16 && vnm_spmm_gather_fp8_ok(T, N, Kfull, M) && Kfull * N < ((int64_t)1 << 32)) {
+    if (M >= 16 && vnm_spmm_gather_fp8_ok(T, N, Kfull, M) && Kfull * N < ((int64_t)1 << 31)) {
         // contract over the 4 Kfull / M kept columns only, gathering their rows of the [Kfull, N] codes (the fp8 step's kernel for wide blocks)
         if (!w_kmajor) {
             LAUNCH(launch_transpose_u8(Wq, N, Kfull, Kfull, wt, s), "vnm_spmm_fp8/transpose");
@@ -468,7 +468,7 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     REQUIRE(scale_ok(sc->x) && scale_ok(sc->w1) && scale_ok(sc->w2) && scale_ok(sc->y2) && scale_ok(sc->dy) && scale_ok(sc->dy1), SFFN_EINVAL,
             "ffn_sparse_step_fp8: scales must be positive finite floats");
     const int64_t T = cfg->T, D = cfg->D, F = cfg->F, E = n_experts;
-    REQUIRE(fits_int(T) && fits_int(D) && fits_int(F * E) && T / 64 < 65536 && F * D < ((int64_t)1 << 32) && T * D < ((int64_t)1 << 32), SFFN_EUNSUPPORTED,
+    REQUIRE(fits_int(T) && fits_int(D) && fits_int(F * E) && T / 64 < 65536 && F * D < ((int64_t)1 << 31) && T * D < ((int64_t)1 << 31), SFFN_EUNSUPPORTED,
             "ffn_sparse_step_fp8: dimension too large");
     GemmGroup g;                                    // g.n = 0: plain step
     if (seg) {
@@ -935,7 +935,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     REQUIRE(cfg->T < 65536 && fits_int(cfg->F * n_experts) && fits_int(cfg->D), SFFN_EUNSUPPORTED,
             "ffn_sparse_step: T must be below 65536 and F * n_experts below 2^31");
     const int64_t T = cfg->T, D = cfg->D, F = cfg->F, E = n_experts;
-    REQUIRE(cfg->M != 8 || F * D * 2 < ((int64_t)1 << 32), SFFN_EUNSUPPORTED, "ffn_sparse_step: a weight matrix must stay below 4 GiB");
+    REQUIRE(cfg->M != 8 || F * D * 2 < ((int64_t)1 << 31), SFFN_EUNSUPPORTED, "ffn_sparse_step: a weight matrix must stay below 2 GiB");
     REQUIRE(workspace && ws_bytes >= L.total, SFFN_EWORKSPACE, "ffn_sparse_step: workspace missing or too small");
     GemmGroup g;                                    // g.n = 0: plain step
     if (seg) {
@@ -1024,7 +1024,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
         STAGE(launch_sqrelu_vnm_compress_m(y1, T, F, M, y2v, y2m, cix, s), "step/sqrelu_vnm_compress");               // eq. (2), Section 2.3
         // eqs. (3), (7): gather the kept rows of the dense operand (matrix work and traffic shrink with 4 / M); shapes the
         // gathered kernel does not cover re-express the activation as plain 2:4 over all F columns instead
-        const bool gather = vnm_spmm_gather_ok(T, D, F, M) && F * D * 2 < ((int64_t)1 << 32);
+        const bool gather = vnm_spmm_gather_ok(T, D, F, M) && F * D * 2 < ((int64_t)1 << 31);
         if (gather) {
             STAGE(launch_transpose(W2, D, F, F, w1t, 0, nullptr, s), "step/W2.T");
             STAGE(launch_vnm_spmm_gather(y2v, y2m, cix, w1t, D, T, D, F, M, Y3, D, s), "step/y3");                    // eq. (3)

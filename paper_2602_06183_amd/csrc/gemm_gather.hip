@@ -415,7 +415,7 @@ bool vnm_spmm_gather_ok(int64_t T, int64_t N, int64_t F, int M) {
 
 hipError_t launch_vnm_spmm_gather(const uint16_t* a_vals, const uint8_t* a_meta, const uint8_t* colidx, const uint16_t* Wk, int64_t ldw,
                                   int64_t T, int64_t N, int64_t F, int M, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp) {
-    if (!vnm_spmm_gather_ok(T, N, F, M) || ldw < N || F * ldw * 2 >= ((int64_t)1 << 32)) return hipErrorInvalidValue;
+    if (!vnm_spmm_gather_ok(T, N, F, M) || ldw < N || F * ldw * 2 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     const GemmGroup g = grp ? *grp : GemmGroup();
     if (g.n && (g.role != 0 || g.seg_dev || g.n > GemmGroup::kMaxExperts)) return hipErrorInvalidValue;
     const int Kc = (int)(4 * F / M), logM = M == 8 ? 3 : M == 16 ? 4 : M == 32 ? 5 : 6;
@@ -432,7 +432,7 @@ bool vnm_spmm_gather_fp8_ok(int64_t T, int64_t N, int64_t F, int M) {
 
 hipError_t launch_vnm_spmm_gather_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* colidx, const uint8_t* Wq, int64_t ldw, float alpha,
                                       int64_t T, int64_t N, int64_t F, int M, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp) {
-    if (!vnm_spmm_gather_fp8_ok(T, N, F, M) || ldw < N || ldw % 16 != 0 || F * ldw >= ((int64_t)1 << 32)) return hipErrorInvalidValue;
+    if (!vnm_spmm_gather_fp8_ok(T, N, F, M) || ldw < N || ldw % 16 != 0 || F * ldw >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     const GemmGroup g = grp ? *grp : GemmGroup();
     if (g.n && (g.role != 0 || g.seg_dev || g.n > GemmGroup::kMaxExperts)) return hipErrorInvalidValue;
     const int Kc = (int)(4 * F / M), logM = M == 8 ? 3 : M == 16 ? 4 : M == 32 ? 5 : 6;

@@ -317,12 +317,12 @@ __global__ void __launch_bounds__(512) vnm8_gemm_kernel(const uint16_t* __restri
 }
 
 bool vnm8_gemm_ok(int64_t T, int64_t N, int64_t F, int64_t ldw) {
-    // (32-bit offsets inside the kernel: the dense operand and the offsets array stay below 4 GiB)
-    return T > 0 && T % 64 == 0 && N > 0 && N % 64 == 0 && F > 0 && F % 64 == 0 && ldw >= N && ldw % 8 == 0 && F * ldw * 2 < ((int64_t)1 << 32) &&
+    // (32-bit offsets inside the kernel: the dense operand and the offsets array stay below 2 GiB, so every offset is also a non-negative int)
+    return T > 0 && T % 64 == 0 && N > 0 && N % 64 == 0 && F > 0 && F % 64 == 0 && ldw >= N && ldw % 8 == 0 && F * ldw * 2 < ((int64_t)1 << 31) &&
            T * F < ((int64_t)1 << 38);
 }
 bool vnm8_gemm_fp8_ok(int64_t T, int64_t N, int64_t F, int64_t ldw) {
-    return T > 0 && T % 64 == 0 && N > 0 && N % 64 == 0 && F > 0 && F % 128 == 0 && ldw >= N && ldw % 16 == 0 && F * ldw < ((int64_t)1 << 32) &&
+    return T > 0 && T % 64 == 0 && N > 0 && N % 64 == 0 && F > 0 && F % 128 == 0 && ldw >= N && ldw % 16 == 0 && F * ldw < ((int64_t)1 << 31) &&
            T * F < ((int64_t)1 << 38);
 }
 

@@ -69,7 +69,7 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     bad = binding._Cfg(512, 250, 1024, 64, 8, 0, 0)
     assert lib.ffn_sparse_step(ctypes.byref(bad), *args, fake, 1 << 30, None) == -1
     assert len(lib.sffn_last_error()) > 0
-    huge = binding._Cfg(64, 32768, 65536, 64, 8, 0, 0)                    # a 4 GiB weight matrix: beyond the 32-bit offsets of the V:2:8 kernel's loads
+    huge = binding._Cfg(64, 16384, 65536, 64, 8, 0, 0)                    # a 2 GiB weight matrix: beyond the 31-bit offsets of the V:2:8 kernel's loads
     assert lib.ffn_sparse_step(ctypes.byref(huge), *args, fake, 1 << 50, None) == -2
     assert lib.ffn_sparse_step(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 8, 0, 64)), *args, fake, 1 << 40, None) == -1        # unknown flag
     # Alg. 1 / Alg. 2 as separate calls: each half checks its own pointers, the workspace and the path before any launch
