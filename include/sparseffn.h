@@ -347,34 +347,46 @@ int ffn_sparse_step_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* s
  * give the same bits in every output and intermediate.
  *   forward  = Alg. 1, eqs. (1)-(3): X, W1, W2, b1 -> Y3.  It also packs W2.T (Alg. 2 line 2), because that pass over W2 is the one that
  *              writes the W2.T copy eq. (3) reads.  SFFN_FLAG_WEIGHTS_PACKED applies to this call.
- *   backward = Alg. 2, eqs. (4)-(8): dY -> dX, dW1, dW2, on the workspace that the forward call of the same cfg (and segments) left:
- *              what Alg. 2 line 1 saves (y2's packed form, y1 at its kept slots, X.T) and the packed W2.T.  The bf16 form reads the dense
- *              W1 in place (eq. (7)); the fp8 form reads the codes of W1 that its forward call wrote and takes no weight argument.
- * The caller keeps the workspace untouched between the two calls (one workspace per layer in flight); the library cannot check that.
- * Arguments, shapes, alignment, error codes: those of the one-call entry points.  Not built for the unfused wide-block path
- * (SFFN_EUNSUPPORTED) nor for the router's step.  fp8: the forward call writes amax[0..3] (x, w1, w2, y2) and leaves amax[4], amax[5]
- * alone, the backward call writes amax[4], amax[5] (dy, dy1) only. */
+ *   backward = Alg. 2, eqs. (4)-(8): dY -> dX, dW1, dW2.  The bf16 form reads the dense W1 in place (eq. (7)); the fp8 form reads the
+ *              codes of W1 that its forward call wrote and takes no weight argument.
+ * The one-call step's workspace is three regions with different lifetimes, and these calls take them as three DEVICE buffers
+ * (256-byte aligned; sizes from sffn_buffer_sizes / sffn_fp8_buffer_sizes, which fill the *_bytes fields and clear the pointers):
+ *   scratch  nothing in it outlives a call: every layer and micro-batch on a stream can hand over the same buffer;
+ *   saved    written by forward, read by backward: what Alg. 2 line 1 saves (y2's metadata and column offsets, y1 at y2's kept slots, X.T,
+ *            the compacted y2v.T).  One per layer and micro-batch in flight; the caller keeps it untouched between the two calls;
+ *   weights  written by a forward call without SFFN_FLAG_WEIGHTS_PACKED (both packed weights, W2.T; fp8: W1's codes too), read by that
+ *            call, by its backward call and by every later call with the flag.  One per layer, good until the weights change.
+ * The library cannot check what the buffers hold.  Arguments, shapes, alignment, error codes otherwise: those of the one-call entry
+ * points (a missing or short buffer: SFFN_EWORKSPACE).  Not built for the unfused wide-block path (SFFN_EUNSUPPORTED) nor for the
+ * router's step.  fp8: the forward call writes amax[0..3] (x, w1, w2, y2) and leaves amax[4], amax[5] alone, the backward call writes
+ * amax[4], amax[5] (dy, dy1) only. */
+typedef struct sffn_buffers {
+    void*  scratch;  size_t scratch_bytes;
+    void*  saved;    size_t saved_bytes;
+    void*  weights;  size_t weights_bytes;
+} sffn_buffers;
+int sffn_buffer_sizes(const sffn_cfg* cfg, int n_experts, sffn_buffers* out);        /* n_experts = 1: the plain step */
+int sffn_fp8_buffer_sizes(const sffn_cfg* cfg, int n_experts, sffn_buffers* out);
 int ffn_sparse_forward(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, const uint16_t* W2, const float* b1,
-                       uint16_t* Y3, void* workspace, size_t ws_bytes, void* stream);
+                       uint16_t* Y3, const sffn_buffers* buf, void* stream);
 int ffn_sparse_backward(const sffn_cfg* cfg, const uint16_t* W1, const uint16_t* dY, uint16_t* dX, uint16_t* dW1,
-                        uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
+                        uint16_t* dW2, const sffn_buffers* buf, void* stream);
 int ffn_sparse_forward_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* seg_offsets, const uint16_t* X,
-                               const uint16_t* W1, const uint16_t* W2, const float* b1, uint16_t* Y3, void* workspace,
-                               size_t ws_bytes, void* stream);
+                               const uint16_t* W1, const uint16_t* W2, const float* b1, uint16_t* Y3, const sffn_buffers* buf,
+                               void* stream);
 int ffn_sparse_backward_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* seg_offsets, const uint16_t* W1,
-                                const uint16_t* dY, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace,
-                                size_t ws_bytes, void* stream);
+                                const uint16_t* dY, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, const sffn_buffers* buf,
+                                void* stream);
 int ffn_sparse_forward_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* scales, const uint16_t* X, const uint16_t* W1,
-                           const uint16_t* W2, const float* b1, uint16_t* Y3, void* workspace, size_t ws_bytes, float* amax,
-                           void* stream);
+                           const uint16_t* W2, const float* b1, uint16_t* Y3, const sffn_buffers* buf, float* amax, void* stream);
 int ffn_sparse_backward_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* scales, const uint16_t* dY, uint16_t* dX,
-                            uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, float* amax, void* stream);
+                            uint16_t* dW1, uint16_t* dW2, const sffn_buffers* buf, float* amax, void* stream);
 int ffn_sparse_forward_fp8_grouped(const sffn_cfg* cfg, const sffn_fp8_scales* scales, int n_experts,
                                    const int64_t* seg_offsets, const uint16_t* X, const uint16_t* W1, const uint16_t* W2,
-                                   const float* b1, uint16_t* Y3, void* workspace, size_t ws_bytes, float* amax, void* stream);
+                                   const float* b1, uint16_t* Y3, const sffn_buffers* buf, float* amax, void* stream);
 int ffn_sparse_backward_fp8_grouped(const sffn_cfg* cfg, const sffn_fp8_scales* scales, int n_experts,
                                     const int64_t* seg_offsets, const uint16_t* dY, uint16_t* dX, uint16_t* dW1,
-                                    uint16_t* dW2, void* workspace, size_t ws_bytes, float* amax, void* stream);
+                                    uint16_t* dW2, const sffn_buffers* buf, float* amax, void* stream);
 
 /* Measurement aid (not part of the method): when enabled, ffn_sparse_step records a HIP event on the
  * caller's stream behind every kernel launch.  sffn_profile_read() waits for the last event of the

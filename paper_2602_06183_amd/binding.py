@@ -17,6 +17,11 @@ class SffnError(RuntimeError):
     pass
 
 
+class _Buffers(ctypes.Structure):
+    _fields_ = [("scratch", ctypes.c_void_p), ("scratch_bytes", ctypes.c_size_t), ("saved", ctypes.c_void_p), ("saved_bytes", ctypes.c_size_t),
+                ("weights", ctypes.c_void_p), ("weights_bytes", ctypes.c_size_t)]
+
+
 class _Cfg(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int64), ("D", ctypes.c_int64), ("F", ctypes.c_int64), ("V", ctypes.c_int32),
                 ("M", ctypes.c_int32), ("mode", ctypes.c_int32), ("flags", ctypes.c_int32)]
@@ -112,15 +117,17 @@ def load():
     lib.ffn_sparse_step_fp8.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Scales), p, p, p, p, p, p, p, p, p, p, sz, p, p]
     lib.sffn_fp8_grouped_workspace_layout.argtypes = [ctypes.POINTER(_Cfg), i32, ctypes.POINTER(_Fp8Layout)]
     lib.ffn_sparse_step_fp8_grouped.argtypes = [ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Scales), i32, p, p, p, p, p, p, p, p, p, p, p, sz, p, p]
-    cfgp, scp, segp = ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Scales), ctypes.POINTER(ctypes.c_int64)
-    lib.ffn_sparse_forward.argtypes = [cfgp] + [p] * 5 + [p, sz, p]
-    lib.ffn_sparse_backward.argtypes = [cfgp] + [p] * 5 + [p, sz, p]
-    lib.ffn_sparse_forward_grouped.argtypes = [cfgp, i32, segp] + [p] * 5 + [p, sz, p]
-    lib.ffn_sparse_backward_grouped.argtypes = [cfgp, i32, segp] + [p] * 5 + [p, sz, p]
-    lib.ffn_sparse_forward_fp8.argtypes = [cfgp, scp] + [p] * 5 + [p, sz, p, p]
-    lib.ffn_sparse_backward_fp8.argtypes = [cfgp, scp] + [p] * 4 + [p, sz, p, p]
-    lib.ffn_sparse_forward_fp8_grouped.argtypes = [cfgp, scp, i32, segp] + [p] * 5 + [p, sz, p, p]
-    lib.ffn_sparse_backward_fp8_grouped.argtypes = [cfgp, scp, i32, segp] + [p] * 4 + [p, sz, p, p]
+    cfgp, scp, segp, bufp = ctypes.POINTER(_Cfg), ctypes.POINTER(_Fp8Scales), ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(_Buffers)
+    lib.sffn_buffer_sizes.argtypes = [cfgp, i32, bufp]
+    lib.sffn_fp8_buffer_sizes.argtypes = [cfgp, i32, bufp]
+    lib.ffn_sparse_forward.argtypes = [cfgp] + [p] * 5 + [bufp, p]
+    lib.ffn_sparse_backward.argtypes = [cfgp] + [p] * 5 + [bufp, p]
+    lib.ffn_sparse_forward_grouped.argtypes = [cfgp, i32, segp] + [p] * 5 + [bufp, p]
+    lib.ffn_sparse_backward_grouped.argtypes = [cfgp, i32, segp] + [p] * 5 + [bufp, p]
+    lib.ffn_sparse_forward_fp8.argtypes = [cfgp, scp] + [p] * 5 + [bufp, p, p]
+    lib.ffn_sparse_backward_fp8.argtypes = [cfgp, scp] + [p] * 4 + [bufp, p, p]
+    lib.ffn_sparse_forward_fp8_grouped.argtypes = [cfgp, scp, i32, segp] + [p] * 5 + [bufp, p, p]
+    lib.ffn_sparse_backward_fp8_grouped.argtypes = [cfgp, scp, i32, segp] + [p] * 4 + [bufp, p, p]
     lib.sffn_dense_sqrelu.argtypes = [p, p, i64, p]
     lib.sffn_dense_dsqrelu.argtypes = [p, p, p, i64, p]
     lib.sffn_profile_enable.argtypes = [i32]
@@ -216,6 +223,58 @@ def dense_dsqrelu(dy2, y1, out):
 
 def _cfg(T, D, F, mode=MODE_HARD, V=64, M=8, flags=0):
     return _Cfg(T, D, F, V, M, mode, flags)
+
+
+class _StepBuffers:
+    """The three regions of a step's workspace (scratch | saved | weights, in the order of the layout's offsets).  Without `scratch` they are
+    one allocation (`ws`), which is also what the one-call entry points take; with `scratch` (a uint8 CUDA tensor that several step objects may
+    share: nothing in it outlives a call) the saved and weights regions are this object's own and only forward() / backward() can run."""
+
+    def _alloc_regions(self, sizes_fn, n_experts, device, scratch, weights_of=None):
+        b = _Buffers()
+        _check(sizes_fn(ctypes.byref(self.cfg), n_experts, ctypes.byref(b)))
+        self._b1, self._b2 = b.scratch_bytes, b.scratch_bytes + b.saved_bytes
+        total = self._b2 + b.weights_bytes
+        if scratch is None and weights_of is None:
+            self.ws = _u8((total,), device)
+            self._scratch, self._saved, self._weights = self.ws[:self._b1], self.ws[self._b1:self._b2], self.ws[self._b2:]
+        else:
+            if scratch is None:
+                scratch = _u8((b.scratch_bytes,), device)
+            if scratch.dtype != torch.uint8 or not scratch.is_cuda or scratch.numel() < b.scratch_bytes or scratch.data_ptr() % 256:
+                raise SffnError("scratch must be a 256-byte aligned uint8 CUDA tensor of at least %d bytes" % b.scratch_bytes)
+            if weights_of is not None and weights_of._weights.numel() != b.weights_bytes:
+                raise SffnError("weights_of: that step object has another shape")
+            self.ws = None
+            self._scratch, self._saved = scratch, _u8((b.saved_bytes,), device)
+            # weights_of: another micro-batch of the same layer; the packed weights are that object's (it calls forward() first, this one
+            # then runs forward(..., weights_packed=True))
+            self._weights = weights_of._weights if weights_of is not None else _u8((b.weights_bytes,), device)
+        b.scratch, b.saved, b.weights = self._scratch.data_ptr(), self._saved.data_ptr(), self._weights.data_ptr()
+        b.scratch_bytes = self._scratch.numel()
+        self._buf = b
+        return total
+
+    def _one_buffer(self):
+        if self.ws is None:
+            raise SffnError("this step object was built on a shared scratch buffer: use forward() / backward()")
+        return _ptr(self.ws)
+
+    def _region_bytes(self, off, nbytes):
+        """nbytes at layout offset `off`, wherever its region lives."""
+        if off < self._b1:
+            return self._scratch[off:off + nbytes]
+        if off < self._b2:
+            return self._saved[off - self._b1:off - self._b1 + nbytes]
+        return self._weights[off - self._b2:off - self._b2 + nbytes]
+
+
+def buffer_sizes(T, D, F, mode=MODE_HARD, M=8, keep_dense=False, lean=False, n_experts=1, fp8=False, wgrad_fp8=False):
+    """Bytes of the three buffers of the split forward / backward calls: dict(scratch, saved, weights)."""
+    flags = (FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_LEAN if lean else 0) | (FLAG_FP8_WGRAD if (fp8 and wgrad_fp8) else 0)
+    c, b = _cfg(T, D, F, mode, M=M, flags=flags), _Buffers()
+    _check((load().sffn_fp8_buffer_sizes if fp8 else load().sffn_buffer_sizes)(ctypes.byref(c), n_experts, ctypes.byref(b)))
+    return dict(scratch=b.scratch_bytes, saved=b.saved_bytes, weights=b.weights_bytes)
 
 
 def _cfg_with(cfg, weights_packed):
@@ -364,19 +423,21 @@ def vnm_wgrad(a_vals, a_meta, a_colidx, G, out_f_major, V=64, M=8):
     return out
 
 
-class FfnStep:
+class FfnStep(_StepBuffers):
     """Pre-allocated outputs and workspace for repeated ffn_sparse_step calls on one shape."""
 
-    def __init__(self, T, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8, unfused=False, lean=False):
+    def __init__(self, T, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8, unfused=False, lean=False, scratch=None, weights_of=None):
         """keep_dense: also store the dense y1 and dy2 (SFFN_FLAG_KEEP_DENSE); otherwise only y1 at y2's kept
         slots is saved for the backward pass.  M: V:N:M block width, 8, 16, 32 or 64.  unfused (M >= 16): the path
         with separate eq. (2) / eq. (6) kernels that always stores y1 and dy2 and produces no y1_kept.  lean:
         the canonical copies of the packed weights (and, at M = 8, of the packed activations) are not written (SFFN_FLAG_LEAN);
-        saved() then holds stale data for them."""
+        saved() then holds stale data for them.  scratch: a uint8 CUDA tensor to use as the scratch region (see _StepBuffers); layers whose
+        calls are ordered on one stream can share it, each keeping only its saved and weights regions.  weights_of: another FfnStep of the same
+        configuration whose weights region this object shares (a second micro-batch of one layer)."""
         self.T, self.D, self.F, self.mode, self.keep_dense, self.M = T, D, F, mode, keep_dense, M
         self.cfg = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused, lean))
         self.layout = workspace_layout(T, D, F, mode, M, keep_dense, unfused)
-        self.ws = _u8((self.layout["total"],), device)
+        assert self._alloc_regions(load().sffn_buffer_sizes, 1, device, scratch, weights_of) == self.layout["total"]
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
         self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
 
@@ -388,7 +449,7 @@ class FfnStep:
         _want("ffn_sparse_step: b1", b1, (F,), _F32, optional=True)
         _want("ffn_sparse_step: dY", dY, (T, D), _BF16)
         _check(load().ffn_sparse_step(ctypes.byref(_cfg_with(self.cfg, weights_packed)), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY), _ptr(self.Y3),
-                                      _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _stream()))
+                                      _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), self._one_buffer(), self.layout["total"], _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
 
     def forward(self, X, W1, W2, b1, weights_packed=False):
@@ -399,7 +460,7 @@ class FfnStep:
         _want("ffn_sparse_forward: W2", W2, (D, F), _BF16)
         _want("ffn_sparse_forward: b1", b1, (F,), _F32, optional=True)
         _check(load().ffn_sparse_forward(ctypes.byref(_cfg_with(self.cfg, weights_packed)), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(self.Y3),
-                                         _ptr(self.ws), self.layout["total"], _stream()))
+                                         ctypes.byref(self._buf), _stream()))
         return self.Y3
 
     def backward(self, W1, dY):
@@ -408,7 +469,7 @@ class FfnStep:
         _want("ffn_sparse_backward: W1", W1, (F, D), _BF16)
         _want("ffn_sparse_backward: dY", dY, (T, D), _BF16)
         _check(load().ffn_sparse_backward(ctypes.byref(self.cfg), _ptr(W1), _ptr(dY), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2),
-                                          _ptr(self.ws), self.layout["total"], _stream()))
+                                          ctypes.byref(self._buf), _stream()))
         return self.dX, self.dW1, self.dW2
 
     def saved(self):
@@ -420,7 +481,7 @@ class FfnStep:
             for s in shape:
                 n *= s
             nbytes = n * (2 if dtype == torch.bfloat16 else 1)
-            return self.ws[off:off + nbytes].view(dtype).view(shape)
+            return self._region_bytes(off, nbytes).view(dtype).view(shape)
 
         out = dict(w1_vals=view(L["w1_vals"], (F, D // 2), torch.bfloat16), w1_meta=view(L["w1_meta"], (F, D // 8), torch.uint8),
                    w2t_vals=view(L["w2t_vals"], (F, D // 2), torch.bfloat16), w2t_meta=view(L["w2t_meta"], (F, D // 8), torch.uint8),
@@ -434,11 +495,11 @@ class FfnStep:
         return out
 
 
-class FfnStepGrouped:
+class FfnStepGrouped(_StepBuffers):
     """Pre-allocated outputs and workspace for ffn_sparse_step_grouped: n_experts FFNs, expert e on token rows
     seg[e]..seg[e+1] (host integers, multiples of 64; T = seg[-1])."""
 
-    def __init__(self, seg, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8, lean=False):
+    def __init__(self, seg, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8, lean=False, scratch=None):
         self.seg = [int(v) for v in seg]
         self.E, self.T, self.D, self.F, self.mode, self.keep_dense, self.M = len(self.seg) - 1, self.seg[-1], D, F, mode, keep_dense, M
         self.seg_c = (ctypes.c_int64 * len(self.seg))(*self.seg)
@@ -446,7 +507,7 @@ class FfnStepGrouped:
         lay = _Layout()
         _check(load().sffn_grouped_workspace_layout(ctypes.byref(self.cfg), self.E, ctypes.byref(lay)))
         self.layout = {n: getattr(lay, n) for n, _ in _Layout._fields_}
-        self.ws = _u8((self.layout["total"],), device)
+        assert self._alloc_regions(load().sffn_buffer_sizes, self.E, device, scratch) == self.layout["total"]
         self.Y3, self.dX = _bf16((self.T, D), device), _bf16((self.T, D), device)
         self.dW1, self.dW2 = _bf16((self.E, F, D), device), _bf16((self.E, D, F), device)
 
@@ -458,8 +519,7 @@ class FfnStepGrouped:
         _want("ffn_sparse_step_grouped: b1", b1, (E, F), _F32, optional=True)
         _want("ffn_sparse_step_grouped: dY", dY, (T, D), _BF16)
         _check(load().ffn_sparse_step_grouped(ctypes.byref(_cfg_with(self.cfg, weights_packed)), self.E, self.seg_c, _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1),
-                                              _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws),
-                                              self.layout["total"], _stream()))
+                                              _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), self._one_buffer(), self.layout["total"], _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
 
     def forward(self, X, W1, W2, b1, weights_packed=False):
@@ -470,7 +530,7 @@ class FfnStepGrouped:
         _want("ffn_sparse_forward_grouped: W2", W2, (E, D, F), _BF16)
         _want("ffn_sparse_forward_grouped: b1", b1, (E, F), _F32, optional=True)
         _check(load().ffn_sparse_forward_grouped(ctypes.byref(_cfg_with(self.cfg, weights_packed)), self.E, self.seg_c, _ptr(X), _ptr(W1), _ptr(W2),
-                                                 _ptr(b1), _ptr(self.Y3), _ptr(self.ws), self.layout["total"], _stream()))
+                                                 _ptr(b1), _ptr(self.Y3), ctypes.byref(self._buf), _stream()))
         return self.Y3
 
     def backward(self, W1, dY):
@@ -479,7 +539,7 @@ class FfnStepGrouped:
         _want("ffn_sparse_backward_grouped: W1", W1, (E, F, D), _BF16)
         _want("ffn_sparse_backward_grouped: dY", dY, (T, D), _BF16)
         _check(load().ffn_sparse_backward_grouped(ctypes.byref(self.cfg), self.E, self.seg_c, _ptr(W1), _ptr(dY), _ptr(self.dX), _ptr(self.dW1),
-                                                  _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _stream()))
+                                                  _ptr(self.dW2), ctypes.byref(self._buf), _stream()))
         return self.dX, self.dW1, self.dW2
 
     def saved(self):
@@ -491,7 +551,7 @@ class FfnStepGrouped:
             for s in shape:
                 n *= s
             nbytes = n * (2 if dtype == torch.bfloat16 else 1)
-            return self.ws[off:off + nbytes].view(dtype).view(shape)
+            return self._region_bytes(off, nbytes).view(dtype).view(shape)
 
         out = dict(w1_vals=view(L["w1_vals"], (E, F, D // 2), torch.bfloat16), w1_meta=view(L["w1_meta"], (E, F, D // 8), torch.uint8),
                    w2t_vals=view(L["w2t_vals"], (E, F, D // 2), torch.bfloat16), w2t_meta=view(L["w2t_meta"], (E, F, D // 8), torch.uint8),
@@ -579,11 +639,11 @@ def vnm_spmm_fp8(a_codes, a_meta, a_colidx, scale_a, Wq, scale_w, w_kmajor, V=64
     return out
 
 
-class FfnStepFp8:
+class FfnStepFp8(_StepBuffers):
     """ffn_sparse_step_fp8 with outputs and workspace allocated once.  scales: dict with the six per-tensor scales
     x, w1, w2, y2, dy, dy1 (positive floats; delayed scaling: the caller derives them from earlier steps)."""
 
-    def __init__(self, T, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False, M=8):
+    def __init__(self, T, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False, M=8, scratch=None):
         """wgrad_fp8: eqs. (5), (8) contract codes as well (SFFN_FLAG_FP8_WGRAD); otherwise they are the bf16 contractions.
         lean: the canonical copies of the packed tensors are not written (SFFN_FLAG_LEAN).  M: columns per V:N:M block (8, 16, 32, 64)."""
         self.T, self.D, self.F, self.mode, self.M = T, D, F, mode, M
@@ -593,7 +653,7 @@ class FfnStepFp8:
         _check(load().sffn_fp8_workspace_layout(ctypes.byref(self.cfg), ctypes.byref(lay)))
         self.layout = {n: getattr(lay, n) for n, _ in _Fp8Layout._fields_}
         self.keep_dense = keep_dense
-        self.ws = _u8((self.layout["total"],), device)
+        assert self._alloc_regions(load().sffn_fp8_buffer_sizes, 1, device, scratch) == self.layout["total"]
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
         self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
         self.amax = torch.zeros((8,), dtype=torch.float32, device=device)        # [0:6]: x, w1, w2, y2, dy, dy1 after every call
@@ -615,7 +675,7 @@ class FfnStepFp8:
         _want("ffn_sparse_step_fp8: b1", b1, (F,), _F32, optional=True)
         _want("ffn_sparse_step_fp8: dY", dY, (T, D), _BF16)
         _check(load().ffn_sparse_step_fp8(ctypes.byref(_cfg_with(self.cfg, weights_packed)), ctypes.byref(self.scales), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY),
-                                          _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _ptr(self.amax), _stream()))
+                                          _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), self._one_buffer(), self.layout["total"], _ptr(self.amax), _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
 
     def forward(self, X, W1, W2, b1, weights_packed=False):
@@ -626,14 +686,14 @@ class FfnStepFp8:
         _want("ffn_sparse_forward_fp8: W2", W2, (D, F), _BF16)
         _want("ffn_sparse_forward_fp8: b1", b1, (F,), _F32, optional=True)
         _check(load().ffn_sparse_forward_fp8(ctypes.byref(_cfg_with(self.cfg, weights_packed)), ctypes.byref(self.scales), _ptr(X), _ptr(W1), _ptr(W2),
-                                             _ptr(b1), _ptr(self.Y3), _ptr(self.ws), self.layout["total"], _ptr(self.amax), _stream()))
+                                             _ptr(b1), _ptr(self.Y3), ctypes.byref(self._buf), _ptr(self.amax), _stream()))
         return self.Y3
 
     def backward(self, dY):
         """Alg. 2 alone (ffn_sparse_backward_fp8) on what the last forward() left (W1 is read as the codes that call wrote); amax[4:6] are written."""
         _want("ffn_sparse_backward_fp8: dY", dY, (self.T, self.D), _BF16)
         _check(load().ffn_sparse_backward_fp8(ctypes.byref(self.cfg), ctypes.byref(self.scales), _ptr(dY), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2),
-                                              _ptr(self.ws), self.layout["total"], _ptr(self.amax), _stream()))
+                                              ctypes.byref(self._buf), _ptr(self.amax), _stream()))
         return self.dX, self.dW1, self.dW2
 
     def saved(self):
@@ -645,7 +705,7 @@ class FfnStepFp8:
             for d in shape:
                 n *= d
             nbytes = n * (2 if dtype == torch.bfloat16 else 1)
-            return self.ws[off:off + nbytes].view(dtype).view(shape)
+            return self._region_bytes(off, nbytes).view(dtype).view(shape)
 
         u8 = torch.uint8
         out = dict(w1_codes=view(L["w1_codes"], (F, D // 2), u8), w1_meta=view(L["w1_meta"], (F, D // 8), u8),
@@ -665,7 +725,7 @@ class FfnStepFp8:
 class FfnStepFp8Grouped(FfnStepFp8):
     """ffn_sparse_step_fp8_grouped: n_experts FFNs, expert e on token rows seg[e]..seg[e+1] (host integers, multiples of 64; T = seg[-1])."""
 
-    def __init__(self, seg, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False, M=8):
+    def __init__(self, seg, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False, M=8, scratch=None):
         self.seg = [int(v) for v in seg]
         self.E, self.T, self.D, self.F, self.mode, self.keep_dense, self.M = len(self.seg) - 1, self.seg[-1], D, F, mode, keep_dense, M
         self.seg_c = (ctypes.c_int64 * len(self.seg))(*self.seg)
@@ -674,7 +734,7 @@ class FfnStepFp8Grouped(FfnStepFp8):
         lay = _Fp8Layout()
         _check(load().sffn_fp8_grouped_workspace_layout(ctypes.byref(self.cfg), self.E, ctypes.byref(lay)))
         self.layout = {n: getattr(lay, n) for n, _ in _Fp8Layout._fields_}
-        self.ws = _u8((self.layout["total"],), device)
+        assert self._alloc_regions(load().sffn_fp8_buffer_sizes, self.E, device, scratch) == self.layout["total"]
         self.Y3, self.dX = _bf16((self.T, D), device), _bf16((self.T, D), device)
         self.dW1, self.dW2 = _bf16((self.E, F, D), device), _bf16((self.E, D, F), device)
         self.amax = torch.zeros((8,), dtype=torch.float32, device=device)
@@ -687,8 +747,7 @@ class FfnStepFp8Grouped(FfnStepFp8):
         _want("ffn_sparse_step_fp8_grouped: b1", b1, (E, F), _F32, optional=True)
         _want("ffn_sparse_step_fp8_grouped: dY", dY, (T, D), _BF16)
         _check(load().ffn_sparse_step_fp8_grouped(ctypes.byref(_cfg_with(self.cfg, weights_packed)), ctypes.byref(self.scales), self.E, self.seg_c, _ptr(X), _ptr(W1), _ptr(W2),
-                                                  _ptr(b1), _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws),
-                                                  self.layout["total"], _ptr(self.amax), _stream()))
+                                                  _ptr(b1), _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), self._one_buffer(), self.layout["total"], _ptr(self.amax), _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
 
     def forward(self, X, W1, W2, b1, weights_packed=False):
@@ -699,7 +758,7 @@ class FfnStepFp8Grouped(FfnStepFp8):
         _want("ffn_sparse_forward_fp8_grouped: W2", W2, (E, D, F), _BF16)
         _want("ffn_sparse_forward_fp8_grouped: b1", b1, (E, F), _F32, optional=True)
         _check(load().ffn_sparse_forward_fp8_grouped(ctypes.byref(_cfg_with(self.cfg, weights_packed)), ctypes.byref(self.scales), self.E, self.seg_c,
-                                                     _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(self.Y3), _ptr(self.ws), self.layout["total"],
+                                                     _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(self.Y3), ctypes.byref(self._buf),
                                                      _ptr(self.amax), _stream()))
         return self.Y3
 
@@ -707,7 +766,7 @@ class FfnStepFp8Grouped(FfnStepFp8):
         """Alg. 2 alone for every expert (ffn_sparse_backward_fp8_grouped) on what the last forward() left; amax[4:6] are written."""
         _want("ffn_sparse_backward_fp8_grouped: dY", dY, (self.T, self.D), _BF16)
         _check(load().ffn_sparse_backward_fp8_grouped(ctypes.byref(self.cfg), ctypes.byref(self.scales), self.E, self.seg_c, _ptr(dY), _ptr(self.dX),
-                                                      _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _ptr(self.amax), _stream()))
+                                                      _ptr(self.dW1), _ptr(self.dW2), ctypes.byref(self._buf), _ptr(self.amax), _stream()))
         return self.dX, self.dW1, self.dW2
 
     def saved(self):
@@ -719,7 +778,7 @@ class FfnStepFp8Grouped(FfnStepFp8):
             for d in shape:
                 n *= d
             nbytes = n * (2 if dtype == torch.bfloat16 else 1)
-            return self.ws[off:off + nbytes].view(dtype).view(shape)
+            return self._region_bytes(off, nbytes).view(dtype).view(shape)
 
         u8 = torch.uint8
         out = dict(w1_codes=view(L["w1_codes"], (E, F, D // 2), u8), w1_meta=view(L["w1_meta"], (E, F, D // 8), u8),

@@ -41,11 +41,37 @@ hipEvent_t g_prof_ev[kMaxStages + 1];
 const char* g_prof_name[kMaxStages];
 int g_prof_n = 0;
 
+// The workspace is three regions laid end to end, [scratch | saved | weights] (the split forward / backward calls take them as three buffers):
+//   scratch  nothing in it outlives a call (layers and micro-batches may share one)
+//   saved    what the backward pass reads of the forward pass (Alg. 2 line 1), per layer and micro-batch in flight
+//   weights  what the pruning passes write: per layer, good until the weights change (SFFN_FLAG_WEIGHTS_PACKED reads it)
 struct FullLayout {
     sffn_ws_layout pub;
     // internal operands of the GEMMs, all in the blocked layout
     size_t w1_vblk, w1_mblk, w2t_vblk, w2t_mblk, x_blk, xt_blk, dy_blk, dyt_blk, w2_blk, w1t_blk, a24_vblk, a24_mblk, at_blk, kmask, total;
+    size_t scratch_end, saved_end;      // region boundaries: scratch = [0, scratch_end), saved = [scratch_end, saved_end), weights = [saved_end, total)
 };
+
+// Where the three regions of a step's workspace live: one buffer (the one-call entry points) or three (the split calls)
+struct Regions {
+    unsigned char *scratch = nullptr, *saved = nullptr, *weights = nullptr;
+    size_t scratch_end = 0, saved_end = 0;
+    unsigned char* at(size_t off) const { return off < scratch_end ? scratch + off : off < saved_end ? saved + (off - scratch_end) : weights + (off - saved_end); }
+};
+// buf == nullptr: `workspace` holds [scratch | saved | weights] back to back.  Returns 0 or the error code to hand back.
+inline int place_regions(const sffn_buffers* buf, void* workspace, size_t ws_bytes, size_t scratch_end, size_t saved_end, size_t total, Regions* r) {
+    r->scratch_end = scratch_end; r->saved_end = saved_end;
+    if (!buf) {
+        if (!workspace || ws_bytes < total) return SFFN_EWORKSPACE;
+        r->scratch = (unsigned char*)workspace; r->saved = r->scratch + scratch_end; r->weights = r->scratch + saved_end;
+        return SFFN_OK;
+    }
+    if (!buf->scratch || !buf->saved || !buf->weights) return SFFN_EWORKSPACE;
+    if (buf->scratch_bytes < scratch_end || buf->saved_bytes < saved_end - scratch_end || buf->weights_bytes < total - saved_end) return SFFN_EWORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(buf->scratch) | reinterpret_cast<uintptr_t>(buf->saved) | reinterpret_cast<uintptr_t>(buf->weights)) & 255u) return SFFN_EINVAL;
+    r->scratch = (unsigned char*)buf->scratch; r->saved = (unsigned char*)buf->saved; r->weights = (unsigned char*)buf->weights;
+    return SFFN_OK;
+}
 
 // Blocks of M = 16, 32, 64 columns take the fused path (V:N:M epilogues inside eqs. (1), (4), gathered-row eqs. (3), (7)) when the
 // gathered-row kernel covers the shape and the caller does not ask for the unfused reference path.
@@ -66,22 +92,31 @@ bool make_layout(const sffn_cfg* c, FullLayout* L, int n_experts = 1) {
     const size_t TF = T * (size_t)c->F;                               // ... token x hidden tensors use TF
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
-    L->pub.w1_vals = take(F * D);          L->pub.w1_meta = take(F * D / 8);
-    L->pub.w2t_vals = take(F * D);         L->pub.w2t_meta = take(F * D / 8);
+    // ---- scratch -----------------------------------------------------------------------------------------------------------------------
     L->pub.y1 = take(dense ? TF * 2 : 0);
-    L->pub.y2_vals = take(TF * 4 / M);  L->pub.y2_meta = take(TF / (2 * M));   L->pub.colidx = take(TF / 64 / M * 4);
     L->pub.dy2 = take(dense ? TF * 2 : 0);
+    L->pub.y2_vals = take(TF * 4 / M);
     L->pub.dy1_vals = take(TF * 4 / M);
+    L->x_blk = take(T * D * 2);
+    L->dy_blk = take(T * D * 2);           L->dyt_blk = take(D * T * 2);
+    L->a24_vblk = take(TF);             // M = 8: the survivors in the V:2:8 kernel's units; unfused path: the plain-2:4 view
+    L->w1t_blk = take(fused ? 0 : D * F * 2);      // unfused path only: W2.T or W1.T, row-major
+    L->scratch_end = off;
+    // ---- saved -------------------------------------------------------------------------------------------------------------------------
+    L->pub.y2_meta = take(TF / (2 * M));   L->pub.colidx = take(TF / 64 / M * 4);
     L->pub.y1_kept_bytes = fused ? TF * 4 / M : 0;
     L->pub.y1_kept = take(L->pub.y1_kept_bytes);
-    L->w1_vblk = take(F * D);              L->w1_mblk = take(F * D / 8);
-    L->w2t_vblk = take(F * D);             L->w2t_mblk = take(F * D / 8);
-    L->x_blk = take(T * D * 2);            L->xt_blk = take(D * T * 2);
-    L->dy_blk = take(T * D * 2);           L->dyt_blk = take(D * T * 2);
-    L->w2_blk = take(D * F * 2);           L->w1t_blk = take(D * F * 2);
-    L->a24_vblk = take(TF);             L->a24_mblk = take(TF / 8);
+    L->xt_blk = take(D * T * 2);
+    L->a24_mblk = take(TF / 8);         // M = 8: metadata and regrouped column offsets for the V:2:8 kernel (eq. (7) reads them again)
     L->at_blk = take(M == 8 ? TF : 2 * TF);   // M = 8: transposed activation compacted to the kept hidden units [F / 2, T]; wider: dense [F, T]
     L->kmask = take(TF / 64 / 8);       // kept-column bit mask per (64-token block, group of 8 hidden units)
+    L->saved_end = off;
+    // ---- weights -----------------------------------------------------------------------------------------------------------------------
+    L->pub.w1_vals = take(F * D);          L->pub.w1_meta = take(F * D / 8);
+    L->pub.w2t_vals = take(F * D);         L->pub.w2t_meta = take(F * D / 8);
+    L->w1_vblk = take(F * D);              L->w1_mblk = take(F * D / 8);
+    L->w2t_vblk = take(F * D);             L->w2t_mblk = take(F * D / 8);
+    L->w2_blk = take(fused ? D * F * 2 : 0);       // fused paths: W2.T [F, D] per expert, written by the pruning pass of W2
     L->total = off;
     L->pub.total = off;
     return true;
@@ -419,6 +454,7 @@ namespace {
 struct Fp8Layout {
     sffn_fp8_ws_layout pub;
     size_t w1_blk, w1_mblk, w2t_blk, w2t_mblk, xq, xt_blk, dyq, dyt_blk, w2q, w1tq, v24, m24, at_blk, kmask, amax_slots, total;
+    size_t scratch_end, saved_end;      // [scratch | saved | weights], as in FullLayout
 };
 // E = number of experts (1 for the plain step): weight-shaped tensors hold E matrices back to back
 bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L, int n_experts = 1) {
@@ -429,20 +465,29 @@ bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L, int n_experts = 1) {
     const size_t T = c->T, D = c->D, F = (size_t)c->F * n_experts, TF = T * (size_t)c->F, M = (size_t)c->M;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
+    // ---- scratch -----------------------------------------------------------------------------------------------------------------------
+    L->pub.y1 = take(dense ? TF * 2 : 0);
+    L->pub.dy2 = take(dense ? TF * 2 : 0);
+    L->pub.y2_codes = take(2 * TF / M);
+    L->pub.dy1_vals = take(M == 8 ? TF / 2 : 2 * TF / M);
+    L->xq = take(T * D);                   L->dyq = take(T * D);
+    L->dyt_blk = take(T * D * 2);
+    L->v24 = take(TF / 2);
+    L->amax_slots = take((size_t)6 * 64 * 64 * sizeof(float));      // 6 tensors x 64 slots x 256 bytes
+    L->scratch_end = off;
+    // ---- saved (what the backward pass reads of the forward pass) -------------------------------------------------------------------------
+    L->pub.y2_meta = take(TF / (2 * M));    L->pub.colidx = take(TF / 64 / M * 4);
+    L->pub.y1_kept = take(4 * TF / M);
+    L->xt_blk = take(T * D * 2);
+    L->m24 = take(TF / 8);
+    L->at_blk = take(TF);                  L->kmask = take(TF / 64 / 8);
+    L->saved_end = off;
+    // ---- weights (what the two weight passes write; eq. (7) reads W1's codes from here) ---------------------------------------------------
     L->pub.w1_codes = take(F * D / 2);     L->pub.w1_meta = take(F * D / 8);
     L->pub.w2t_codes = take(F * D / 2);    L->pub.w2t_meta = take(F * D / 8);
-    L->pub.y1 = take(dense ? TF * 2 : 0);
-    L->pub.y2_codes = take(2 * TF / M);    L->pub.y2_meta = take(TF / (2 * M));    L->pub.colidx = take(TF / 64 / M * 4);
-    L->pub.dy2 = take(dense ? TF * 2 : 0);
-    L->pub.dy1_vals = take(M == 8 ? TF / 2 : 2 * TF / M);        L->pub.y1_kept = take(4 * TF / M);
     L->w1_blk = take(F * D / 2);           L->w2t_blk = take(F * D / 2);
     L->w1_mblk = take(F * D / 8);          L->w2t_mblk = take(F * D / 8);
-    L->xq = take(T * D);                   L->xt_blk = take(T * D * 2);
-    L->dyq = take(T * D);                  L->dyt_blk = take(T * D * 2);
     L->w2q = take(D * F);                  L->w1tq = take(D * F);
-    L->v24 = take(TF / 2);                 L->m24 = take(TF / 8);
-    L->at_blk = take(TF);                  L->kmask = take(TF / 64 / 8);
-    L->amax_slots = take((size_t)6 * 64 * 64 * sizeof(float));      // 6 tensors x 64 slots x 256 bytes
     L->total = off;
     L->pub.total = off;
     return true;
@@ -450,7 +495,7 @@ bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L, int n_experts = 1) {
 
 int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, const int64_t* seg, const uint16_t* X, const uint16_t* W1,
                  const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace,
-                 size_t ws_bytes, float* amax, void* stream, int phase = 3) {
+                 size_t ws_bytes, float* amax, void* stream, int phase = 3, const sffn_buffers* buf = nullptr) {
     // phase: bit 0 = Alg. 1 (forward pass), bit 1 = Alg. 2 (backward pass); a split call's halves meet through the workspace
     const bool fwd = (phase & 1) != 0, bwd = (phase & 2) != 0;
     REQUIRE(cfg != nullptr && sc != nullptr, SFFN_EINVAL, "ffn_sparse_step_fp8: cfg or scales is null");
@@ -478,16 +523,20 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
         g.n = (int)E;
         for (int e = 0; e <= E; ++e) g.seg[e] = (int32_t)seg[e];
     }
-    REQUIRE(workspace && ws_bytes >= L.total, SFFN_EWORKSPACE, "ffn_sparse_step_fp8: workspace missing or too small (sffn_fp8_workspace_bytes)");
+    Regions rg;
+    {
+        const int rc = place_regions(buf, workspace, ws_bytes, L.scratch_end, L.saved_end, L.total, &rg);
+        REQUIRE(rc != SFFN_EINVAL, SFFN_EINVAL, "ffn_sparse_forward_fp8 / ffn_sparse_backward_fp8: the three buffers must be 256-byte aligned");
+        REQUIRE(rc == SFFN_OK, SFFN_EWORKSPACE, "ffn_sparse_step_fp8: workspace missing or too small (sffn_fp8_workspace_bytes)");
+    }
     hipStream_t s = (hipStream_t)stream;
-    uint8_t* ws = (uint8_t*)workspace;
-    uint8_t *w1c = ws + L.pub.w1_codes, *w1m = ws + L.pub.w1_meta, *w2c = ws + L.pub.w2t_codes, *w2m = ws + L.pub.w2t_meta;
-    uint16_t *y1 = (uint16_t*)(ws + L.pub.y1), *dy2 = (uint16_t*)(ws + L.pub.dy2), *dy1v = (uint16_t*)(ws + L.pub.dy1_vals), *ykept = (uint16_t*)(ws + L.pub.y1_kept);
-    uint8_t *y2c = ws + L.pub.y2_codes, *y2m = ws + L.pub.y2_meta, *cix = ws + L.pub.colidx;
-    uint8_t *w1mb = ws + L.w1_mblk, *w2mb = ws + L.w2t_mblk;
-    uint8_t *w1b = ws + L.w1_blk, *w2b = ws + L.w2t_blk, *xq = ws + L.xq, *dyq = ws + L.dyq, *w2q = ws + L.w2q, *w1tq = ws + L.w1tq;
-    uint16_t *xtb = (uint16_t*)(ws + L.xt_blk), *dytb = (uint16_t*)(ws + L.dyt_blk), *atb = (uint16_t*)(ws + L.at_blk);
-    uint8_t *v24 = ws + L.v24, *m24 = ws + L.m24, *kmask = ws + L.kmask;
+    uint8_t *w1c = rg.at(L.pub.w1_codes), *w1m = rg.at(L.pub.w1_meta), *w2c = rg.at(L.pub.w2t_codes), *w2m = rg.at(L.pub.w2t_meta);
+    uint16_t *y1 = (uint16_t*)(rg.at(L.pub.y1)), *dy2 = (uint16_t*)(rg.at(L.pub.dy2)), *dy1v = (uint16_t*)(rg.at(L.pub.dy1_vals)), *ykept = (uint16_t*)(rg.at(L.pub.y1_kept));
+    uint8_t *y2c = rg.at(L.pub.y2_codes), *y2m = rg.at(L.pub.y2_meta), *cix = rg.at(L.pub.colidx);
+    uint8_t *w1mb = rg.at(L.w1_mblk), *w2mb = rg.at(L.w2t_mblk);
+    uint8_t *w1b = rg.at(L.w1_blk), *w2b = rg.at(L.w2t_blk), *xq = rg.at(L.xq), *dyq = rg.at(L.dyq), *w2q = rg.at(L.w2q), *w1tq = rg.at(L.w1tq);
+    uint16_t *xtb = (uint16_t*)(rg.at(L.xt_blk)), *dytb = (uint16_t*)(rg.at(L.dyt_blk)), *atb = (uint16_t*)(rg.at(L.at_blk));
+    uint8_t *v24 = rg.at(L.v24), *m24 = rg.at(L.m24), *kmask = rg.at(L.kmask);
     const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
     const bool w8 = (cfg->flags & SFFN_FLAG_FP8_WGRAD) != 0;      // eqs. (5), (8) on codes too: X.T, dY.T and the compact transposed survivors as codes
     if (cfg->flags & SFFN_FLAG_LEAN) {      // no canonical copies of the packed tensors (dy1 stays: eq. (8) in bf16 does not need it either, but it is small)
@@ -505,7 +554,7 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     const GemmGroup* gw = g.n ? &g_wgrad : nullptr;
     // amax[0..5] = largest magnitude of x, w1, w2, y2's survivors, dy, dy1's survivors (what next step's scales are made of)
     // (collected in 64 slots per tensor inside the workspace, folded by the last launch)
-    float* slots = amax ? (float*)(ws + L.amax_slots) : nullptr;
+    float* slots = amax ? (float*)(rg.at(L.amax_slots)) : nullptr;
     auto slot_of = [&](int i) { return slots ? slots + (size_t)i * 64 * 64 : nullptr; };
     float *ax = slot_of(0), *aw1 = slot_of(1), *aw2 = slot_of(2), *ay2 = slot_of(3), *ady = slot_of(4), *ady1 = slot_of(5);
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
@@ -615,25 +664,35 @@ int ffn_sparse_step_fp8_grouped(const sffn_cfg* cfg, const sffn_fp8_scales* sc, 
     return run_fp8_step(cfg, sc, n_experts, seg_offsets, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, ws_bytes, amax, stream);
 }
 
-// Alg. 1 / Alg. 2 as separate calls (other layers run between a layer's forward and backward pass); the halves meet through the workspace
+// Alg. 1 / Alg. 2 as separate calls; the halves meet through the `saved` and `weights` buffers
+int sffn_fp8_buffer_sizes(const sffn_cfg* cfg, int n_experts, sffn_buffers* out) {
+    Fp8Layout L;
+    REQUIRE(out != nullptr, SFFN_EINVAL, "sffn_fp8_buffer_sizes: out is null");
+    REQUIRE(make_fp8_layout(cfg, &L, n_experts), SFFN_EINVAL, "sffn_fp8_buffer_sizes: shape or flags outside what ffn_sparse_step_fp8 accepts");
+    out->scratch = out->saved = out->weights = nullptr;
+    out->scratch_bytes = L.scratch_end; out->saved_bytes = L.saved_end - L.scratch_end; out->weights_bytes = L.total - L.saved_end;
+    return SFFN_OK;
+}
 int ffn_sparse_forward_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* sc, const uint16_t* X, const uint16_t* W1, const uint16_t* W2, const float* b1,
-                           uint16_t* Y3, void* workspace, size_t ws_bytes, float* amax, void* stream) {
-    return run_fp8_step(cfg, sc, 1, nullptr, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, workspace, ws_bytes, amax, stream, 1);
+                           uint16_t* Y3, const sffn_buffers* buf, float* amax, void* stream) {
+    REQUIRE(buf != nullptr, SFFN_EINVAL, "ffn_sparse_forward_fp8: buf is null");
+    return run_fp8_step(cfg, sc, 1, nullptr, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, nullptr, 0, amax, stream, 1, buf);
 }
 int ffn_sparse_backward_fp8(const sffn_cfg* cfg, const sffn_fp8_scales* sc, const uint16_t* dY, uint16_t* dX, uint16_t* dW1, uint16_t* dW2,
-                            void* workspace, size_t ws_bytes, float* amax, void* stream) {
-    return run_fp8_step(cfg, sc, 1, nullptr, nullptr, nullptr, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, amax, stream, 2);
+                            const sffn_buffers* buf, float* amax, void* stream) {
+    REQUIRE(buf != nullptr, SFFN_EINVAL, "ffn_sparse_backward_fp8: buf is null");
+    return run_fp8_step(cfg, sc, 1, nullptr, nullptr, nullptr, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, nullptr, 0, amax, stream, 2, buf);
 }
 int ffn_sparse_forward_fp8_grouped(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, const int64_t* seg_offsets, const uint16_t* X,
-                                   const uint16_t* W1, const uint16_t* W2, const float* b1, uint16_t* Y3, void* workspace, size_t ws_bytes, float* amax,
+                                   const uint16_t* W1, const uint16_t* W2, const float* b1, uint16_t* Y3, const sffn_buffers* buf, float* amax,
                                    void* stream) {
-    REQUIRE(seg_offsets != nullptr, SFFN_EINVAL, "ffn_sparse_forward_fp8_grouped: seg_offsets is null");
-    return run_fp8_step(cfg, sc, n_experts, seg_offsets, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, workspace, ws_bytes, amax, stream, 1);
+    REQUIRE(seg_offsets != nullptr && buf != nullptr, SFFN_EINVAL, "ffn_sparse_forward_fp8_grouped: seg_offsets or buf is null");
+    return run_fp8_step(cfg, sc, n_experts, seg_offsets, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, nullptr, 0, amax, stream, 1, buf);
 }
 int ffn_sparse_backward_fp8_grouped(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, const int64_t* seg_offsets, const uint16_t* dY,
-                                    uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, float* amax, void* stream) {
-    REQUIRE(seg_offsets != nullptr, SFFN_EINVAL, "ffn_sparse_backward_fp8_grouped: seg_offsets is null");
-    return run_fp8_step(cfg, sc, n_experts, seg_offsets, nullptr, nullptr, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, amax, stream, 2);
+                                    uint16_t* dX, uint16_t* dW1, uint16_t* dW2, const sffn_buffers* buf, float* amax, void* stream) {
+    REQUIRE(seg_offsets != nullptr && buf != nullptr, SFFN_EINVAL, "ffn_sparse_backward_fp8_grouped: seg_offsets or buf is null");
+    return run_fp8_step(cfg, sc, n_experts, seg_offsets, nullptr, nullptr, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, nullptr, 0, amax, stream, 2, buf);
 }
 
 // ---- Section 3.3 / Alg. 3: neuron-level experts that emit the V:N:M format ----------------------------------------
@@ -916,7 +975,7 @@ int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint1
 // the plain step).  Every stage is one launch; the GEMMs find their expert from the segment table.
 static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, const uint16_t* X, const uint16_t* W1,
                     const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1,
-                    uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream, int phase = 3) {
+                    uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream, int phase = 3, const sffn_buffers* buf = nullptr) {
     // phase: bit 0 = Alg. 1 (forward pass), bit 1 = Alg. 2 (backward pass); the two halves of a split call meet through the workspace
     const bool fwd = (phase & 1) != 0, bwd = (phase & 2) != 0;
     REQUIRE(cfg && W1 && (!fwd || (X && W2 && Y3)) && (!bwd || (dY && dX && dW1 && dW2)), SFFN_EINVAL, "ffn_sparse_step: null pointer");
@@ -936,7 +995,12 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
             "ffn_sparse_step: T must be below 65536 and F * n_experts below 2^31");
     const int64_t T = cfg->T, D = cfg->D, F = cfg->F, E = n_experts;
     REQUIRE(cfg->M != 8 || F * D * 2 < ((int64_t)1 << 31), SFFN_EUNSUPPORTED, "ffn_sparse_step: a weight matrix must stay below 2 GiB");
-    REQUIRE(workspace && ws_bytes >= L.total, SFFN_EWORKSPACE, "ffn_sparse_step: workspace missing or too small");
+    Regions rg;
+    {
+        const int rc = place_regions(buf, workspace, ws_bytes, L.scratch_end, L.saved_end, L.total, &rg);
+        REQUIRE(rc != SFFN_EINVAL, SFFN_EINVAL, "ffn_sparse_forward / ffn_sparse_backward: the three buffers must be 256-byte aligned");
+        REQUIRE(rc == SFFN_OK, SFFN_EWORKSPACE, "ffn_sparse_step: workspace missing or too small");
+    }
     GemmGroup g;                                    // g.n = 0: plain step
     if (seg) {
         REQUIRE(seg[0] == 0 && seg[E] == T, SFFN_EINVAL, "ffn_sparse_step_grouped: seg_offsets must start at 0 and end at T");
@@ -948,22 +1012,21 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     }
 
     hipStream_t s = (hipStream_t)stream;
-    unsigned char* ws = (unsigned char*)workspace;
-    uint16_t* w1v = (uint16_t*)(ws + L.pub.w1_vals);    uint8_t* w1m = ws + L.pub.w1_meta;
-    uint16_t* w2v = (uint16_t*)(ws + L.pub.w2t_vals);   uint8_t* w2m = ws + L.pub.w2t_meta;
-    uint16_t* y1 = (uint16_t*)(ws + L.pub.y1);
-    uint16_t* y2v = (uint16_t*)(ws + L.pub.y2_vals);    uint8_t* y2m = ws + L.pub.y2_meta;   uint8_t* cix = ws + L.pub.colidx;
-    uint16_t* dy2 = (uint16_t*)(ws + L.pub.dy2);
-    uint16_t* dy1v = (uint16_t*)(ws + L.pub.dy1_vals);
-    uint16_t* w1vb = (uint16_t*)(ws + L.w1_vblk);       uint8_t* w1mb = ws + L.w1_mblk;
-    uint16_t* w2vb = (uint16_t*)(ws + L.w2t_vblk);      uint8_t* w2mb = ws + L.w2t_mblk;
-    uint16_t* xb = (uint16_t*)(ws + L.x_blk);           uint16_t* xtb = (uint16_t*)(ws + L.xt_blk);
-    uint16_t* dyb = (uint16_t*)(ws + L.dy_blk);         uint16_t* dytb = (uint16_t*)(ws + L.dyt_blk);
-    uint16_t* w2b = (uint16_t*)(ws + L.w2_blk);         uint16_t* w1tb = (uint16_t*)(ws + L.w1t_blk);
-    uint16_t* a24v = (uint16_t*)(ws + L.a24_vblk);      uint8_t* a24m = ws + L.a24_mblk;
-    uint16_t* atb = (uint16_t*)(ws + L.at_blk);
-    uint8_t* kmask = ws + L.kmask;
-    uint16_t* ykept = (uint16_t*)(ws + L.pub.y1_kept);
+    uint16_t* w1v = (uint16_t*)(rg.at(L.pub.w1_vals));    uint8_t* w1m = rg.at(L.pub.w1_meta);
+    uint16_t* w2v = (uint16_t*)(rg.at(L.pub.w2t_vals));   uint8_t* w2m = rg.at(L.pub.w2t_meta);
+    uint16_t* y1 = (uint16_t*)(rg.at(L.pub.y1));
+    uint16_t* y2v = (uint16_t*)(rg.at(L.pub.y2_vals));    uint8_t* y2m = rg.at(L.pub.y2_meta);   uint8_t* cix = rg.at(L.pub.colidx);
+    uint16_t* dy2 = (uint16_t*)(rg.at(L.pub.dy2));
+    uint16_t* dy1v = (uint16_t*)(rg.at(L.pub.dy1_vals));
+    uint16_t* w1vb = (uint16_t*)(rg.at(L.w1_vblk));       uint8_t* w1mb = rg.at(L.w1_mblk);
+    uint16_t* w2vb = (uint16_t*)(rg.at(L.w2t_vblk));      uint8_t* w2mb = rg.at(L.w2t_mblk);
+    uint16_t* xb = (uint16_t*)(rg.at(L.x_blk));           uint16_t* xtb = (uint16_t*)(rg.at(L.xt_blk));
+    uint16_t* dyb = (uint16_t*)(rg.at(L.dy_blk));         uint16_t* dytb = (uint16_t*)(rg.at(L.dyt_blk));
+    uint16_t* w2b = (uint16_t*)(rg.at(L.w2_blk));         uint16_t* w1tb = (uint16_t*)(rg.at(L.w1t_blk));
+    uint16_t* a24v = (uint16_t*)(rg.at(L.a24_vblk));      uint8_t* a24m = rg.at(L.a24_mblk);
+    uint16_t* atb = (uint16_t*)(rg.at(L.at_blk));
+    uint8_t* kmask = rg.at(L.kmask);
+    uint16_t* ykept = (uint16_t*)(rg.at(L.pub.y1_kept));
     const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
     // SFFN_FLAG_WEIGHTS_PACKED: the workspace still holds the packed weights (and W2.T) of the previous call: no pruning passes (Section 3.4:
     // the conversion is paid once per optimizer step, not once per micro-batch)
@@ -983,7 +1046,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
         const GemmGroup* gp = g.n ? &g_packed : nullptr;
         const GemmGroup* gr = g.n ? &g_rows : nullptr;
         const GemmGroup* gw = g.n ? &g_wgrad : nullptr;
-        uint16_t* w2t = w1tb;                            // W2.T [F, D] per expert
+        uint16_t* w2t = w2b;                             // W2.T [F, D] per expert
         if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
         const bool lean_w = (cfg->flags & SFFN_FLAG_LEAN) != 0;        // no canonical copies of the packed weights (the packed activations stay: eqs. (3), (7) read them)
         if (fwd) STAGE(launch_transpose(X, T, D, D, xtb, 1, xb, s), "step/X.T");
@@ -1107,24 +1170,35 @@ int ffn_sparse_step(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, 
     return run_step(cfg, 1, nullptr, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, ws_bytes, stream);
 }
 
-// Alg. 1 / Alg. 2 as separate calls (other layers run between a layer's forward and backward pass); the halves meet through the workspace
+// Alg. 1 / Alg. 2 as separate calls (other layers run between a layer's forward and backward pass); the halves meet through the
+// `saved` and `weights` buffers
+int sffn_buffer_sizes(const sffn_cfg* cfg, int n_experts, sffn_buffers* out) {
+    FullLayout L;
+    REQUIRE(out != nullptr, SFFN_EINVAL, "sffn_buffer_sizes: out is null");
+    REQUIRE(make_layout(cfg, &L, n_experts), SFFN_EINVAL, "sffn_buffer_sizes: T, D, F must be positive multiples of 64, V = 64, M in {8, 16, 32, 64}, n_experts >= 1");
+    out->scratch = out->saved = out->weights = nullptr;
+    out->scratch_bytes = L.scratch_end; out->saved_bytes = L.saved_end - L.scratch_end; out->weights_bytes = L.total - L.saved_end;
+    return SFFN_OK;
+}
 int ffn_sparse_forward(const sffn_cfg* cfg, const uint16_t* X, const uint16_t* W1, const uint16_t* W2, const float* b1, uint16_t* Y3,
-                       void* workspace, size_t ws_bytes, void* stream) {
-    return run_step(cfg, 1, nullptr, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, workspace, ws_bytes, stream, 1);
+                       const sffn_buffers* buf, void* stream) {
+    REQUIRE(buf != nullptr, SFFN_EINVAL, "ffn_sparse_forward: buf is null");
+    return run_step(cfg, 1, nullptr, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, nullptr, 0, stream, 1, buf);
 }
 int ffn_sparse_backward(const sffn_cfg* cfg, const uint16_t* W1, const uint16_t* dY, uint16_t* dX, uint16_t* dW1, uint16_t* dW2,
-                        void* workspace, size_t ws_bytes, void* stream) {
-    return run_step(cfg, 1, nullptr, nullptr, W1, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, stream, 2);
+                        const sffn_buffers* buf, void* stream) {
+    REQUIRE(buf != nullptr, SFFN_EINVAL, "ffn_sparse_backward: buf is null");
+    return run_step(cfg, 1, nullptr, nullptr, W1, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, nullptr, 0, stream, 2, buf);
 }
 int ffn_sparse_forward_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* seg_offsets, const uint16_t* X, const uint16_t* W1,
-                               const uint16_t* W2, const float* b1, uint16_t* Y3, void* workspace, size_t ws_bytes, void* stream) {
-    REQUIRE(seg_offsets != nullptr, SFFN_EINVAL, "ffn_sparse_forward_grouped: seg_offsets is null");
-    return run_step(cfg, n_experts, seg_offsets, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, workspace, ws_bytes, stream, 1);
+                               const uint16_t* W2, const float* b1, uint16_t* Y3, const sffn_buffers* buf, void* stream) {
+    REQUIRE(seg_offsets != nullptr && buf != nullptr, SFFN_EINVAL, "ffn_sparse_forward_grouped: seg_offsets or buf is null");
+    return run_step(cfg, n_experts, seg_offsets, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, nullptr, 0, stream, 1, buf);
 }
 int ffn_sparse_backward_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* seg_offsets, const uint16_t* W1, const uint16_t* dY,
-                                uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
-    REQUIRE(seg_offsets != nullptr, SFFN_EINVAL, "ffn_sparse_backward_grouped: seg_offsets is null");
-    return run_step(cfg, n_experts, seg_offsets, nullptr, W1, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, stream, 2);
+                                uint16_t* dX, uint16_t* dW1, uint16_t* dW2, const sffn_buffers* buf, void* stream) {
+    REQUIRE(seg_offsets != nullptr && buf != nullptr, SFFN_EINVAL, "ffn_sparse_backward_grouped: seg_offsets or buf is null");
+    return run_step(cfg, n_experts, seg_offsets, nullptr, W1, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, nullptr, 0, stream, 2, buf);
 }
 
 size_t sffn_grouped_workspace_bytes(const sffn_cfg* cfg, int n_experts) {

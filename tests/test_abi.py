@@ -33,7 +33,8 @@ def test_workspace_queries():
     assert sffn.workspace_bytes(512, 256, 1024) > 0
     assert sffn.workspace_bytes(500, 256, 1024) == 0          # T not a multiple of 64
     lay = sffn.workspace_layout(512, 256, 1024)
-    offs = [lay[k] for k in ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta", "y1", "y2_vals", "y2_meta", "colidx", "dy2", "dy1_vals", "y1_kept")]
+    # the workspace is [scratch | saved | weights]: what outlives nothing, what the backward pass reads of the forward pass, what the pruning passes write
+    offs = [lay[k] for k in ("y1", "dy2", "y2_vals", "dy1_vals", "y2_meta", "colidx", "y1_kept", "w1_vals", "w1_meta", "w2t_vals", "w2t_meta")]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs) and lay["total"] == sffn.workspace_bytes(512, 256, 1024)
     lib = sffn.load()
     assert lib.sffn_vnm_spmm_workspace_bytes(64, 64, 64, 1) == lib.sffn_vnm_spmm_workspace_bytes(64, 64, 64, 0) == 4096 + 512 + 8192
@@ -72,14 +73,29 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     huge = binding._Cfg(64, 16384, 65536, 64, 8, 0, 0)                    # a 2 GiB weight matrix: beyond the 31-bit offsets of the V:2:8 kernel's loads
     assert lib.ffn_sparse_step(ctypes.byref(huge), *args, fake, 1 << 50, None) == -2
     assert lib.ffn_sparse_step(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 8, 0, 64)), *args, fake, 1 << 40, None) == -1        # unknown flag
-    # Alg. 1 / Alg. 2 as separate calls: each half checks its own pointers, the workspace and the path before any launch
-    assert lib.ffn_sparse_forward(ctypes.byref(cfg), fake, fake, fake, fake, fake, fake, 16, None) == -3
-    assert lib.ffn_sparse_forward(ctypes.byref(cfg), None, fake, fake, fake, fake, fake, 1 << 40, None) == -1
-    assert lib.ffn_sparse_backward(ctypes.byref(cfg), fake, fake, fake, fake, fake, fake, 16, None) == -3
-    assert lib.ffn_sparse_backward(ctypes.byref(cfg), fake, None, fake, fake, fake, fake, 1 << 40, None) == -1
-    assert lib.ffn_sparse_backward(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 16, 0, 2)), fake, fake, fake, fake, fake, fake, 1 << 40, None) == -2   # unfused path
-    assert lib.ffn_sparse_forward_grouped(ctypes.byref(cfg), 2, None, fake, fake, fake, fake, fake, fake, 1 << 40, None) == -1
-    assert lib.ffn_sparse_backward_grouped(ctypes.byref(cfg), 2, None, fake, fake, fake, fake, fake, fake, 1 << 40, None) == -1
+    # Alg. 1 / Alg. 2 as separate calls on three buffers (scratch | saved | weights): sizes add up to the one-call workspace, and each half
+    # checks its own pointers, the buffers and the path before any launch
+    sizes = binding._Buffers()
+    assert lib.sffn_buffer_sizes(ctypes.byref(cfg), 1, ctypes.byref(sizes)) == 0
+    assert sizes.scratch_bytes + sizes.saved_bytes + sizes.weights_bytes == lib.sffn_workspace_bytes(ctypes.byref(cfg))
+    assert min(sizes.scratch_bytes, sizes.saved_bytes, sizes.weights_bytes) > 0 and sizes.scratch is None
+    assert lib.sffn_buffer_sizes(ctypes.byref(bad), 1, ctypes.byref(sizes)) == -1
+    assert lib.sffn_buffer_sizes(ctypes.byref(cfg), 1, ctypes.byref(sizes)) == 0
+    good = binding._Buffers(0x1000, sizes.scratch_bytes, 0x2000, sizes.saved_bytes, 0x3000, sizes.weights_bytes)
+    short = binding._Buffers(0x1000, sizes.scratch_bytes, 0x2000, sizes.saved_bytes - 256, 0x3000, sizes.weights_bytes)
+    skew = binding._Buffers(0x1000, sizes.scratch_bytes, 0x2010, sizes.saved_bytes, 0x3000, sizes.weights_bytes)
+    assert lib.ffn_sparse_forward(ctypes.byref(cfg), fake, fake, fake, fake, fake, None, None) == -1
+    assert lib.ffn_sparse_forward(ctypes.byref(cfg), fake, fake, fake, fake, fake, ctypes.byref(short), None) == -3
+    assert lib.ffn_sparse_forward(ctypes.byref(cfg), fake, fake, fake, fake, fake, ctypes.byref(skew), None) == -1
+    assert lib.ffn_sparse_forward(ctypes.byref(cfg), None, fake, fake, fake, fake, ctypes.byref(good), None) == -1
+    assert lib.ffn_sparse_backward(ctypes.byref(cfg), fake, fake, fake, fake, fake, ctypes.byref(short), None) == -3
+    assert lib.ffn_sparse_backward(ctypes.byref(cfg), fake, None, fake, fake, fake, ctypes.byref(good), None) == -1
+    wide_unfused = binding._Cfg(512, 256, 1024, 64, 16, 0, 2)
+    assert lib.sffn_buffer_sizes(ctypes.byref(wide_unfused), 1, ctypes.byref(sizes)) == 0
+    big = binding._Buffers(0x1000, 1 << 40, 0x2000, 1 << 40, 0x3000, 1 << 40)
+    assert lib.ffn_sparse_backward(ctypes.byref(wide_unfused), fake, fake, fake, fake, fake, ctypes.byref(big), None) == -2   # unfused path
+    assert lib.ffn_sparse_forward_grouped(ctypes.byref(cfg), 2, None, fake, fake, fake, fake, fake, ctypes.byref(big), None) == -1
+    assert lib.ffn_sparse_backward_grouped(ctypes.byref(cfg), 2, None, fake, fake, fake, fake, fake, ctypes.byref(big), None) == -1
     # SFFN_FLAG_WEIGHTS_PACKED (16) exists for the fused paths only: the unfused wide-block path (flag 2) refuses it before any launch
     assert lib.ffn_sparse_step(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 16, 0, 2 | 16)), *args, fake, 1 << 40, None) == -2
     # the fp8 step: scales are a host struct; shapes, flags, scales and the workspace are checked before anything is enqueued
@@ -91,12 +107,17 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     assert lib.ffn_sparse_step_fp8(ctypes.byref(binding._Cfg(512, 256, 1280, 64, 64, 0, 0)), ctypes.byref(sc), *args, fake, 1 << 40, None, None) == -1  # 4 F / M = 80
     assert lib.ffn_sparse_step_fp8(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 16, 0, 0)), ctypes.byref(sc), *args, fake, 16, None, None) == -3       # M = 16: workspace
     assert lib.ffn_sparse_step_fp8(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 8, 0, 2)), ctypes.byref(sc), *args, fake, 1 << 40, None, None) == -1   # unknown flag
-    assert lib.ffn_sparse_forward_fp8(ctypes.byref(cfg), ctypes.byref(sc), None, fake, fake, fake, fake, fake, 1 << 40, None, None) == -1
-    assert lib.ffn_sparse_forward_fp8(ctypes.byref(cfg), ctypes.byref(sc), fake, fake, fake, fake, fake, fake, 16, None, None) == -3
-    assert lib.ffn_sparse_backward_fp8(ctypes.byref(cfg), ctypes.byref(sc), fake, fake, fake, None, fake, 1 << 40, None, None) == -1
-    assert lib.ffn_sparse_backward_fp8(ctypes.byref(cfg), ctypes.byref(sc), fake, fake, fake, fake, fake, 16, None, None) == -3
-    assert lib.ffn_sparse_forward_fp8_grouped(ctypes.byref(cfg), ctypes.byref(sc), 2, None, fake, fake, fake, fake, fake, fake, 1 << 40, None, None) == -1
-    assert lib.ffn_sparse_backward_fp8_grouped(ctypes.byref(cfg), ctypes.byref(sc), 2, None, fake, fake, fake, fake, fake, 1 << 40, None, None) == -1
+    f8sizes = binding._Buffers()
+    assert lib.sffn_fp8_buffer_sizes(ctypes.byref(cfg), 1, ctypes.byref(f8sizes)) == 0
+    assert f8sizes.scratch_bytes + f8sizes.saved_bytes + f8sizes.weights_bytes == lib.sffn_fp8_workspace_bytes(ctypes.byref(cfg))
+    f8good = binding._Buffers(0x1000, f8sizes.scratch_bytes, 0x2000, f8sizes.saved_bytes, 0x3000, f8sizes.weights_bytes)
+    f8short = binding._Buffers(0x1000, f8sizes.scratch_bytes, 0x2000, f8sizes.saved_bytes, 0x3000, f8sizes.weights_bytes - 256)
+    assert lib.ffn_sparse_forward_fp8(ctypes.byref(cfg), ctypes.byref(sc), None, fake, fake, fake, fake, ctypes.byref(f8good), None, None) == -1
+    assert lib.ffn_sparse_forward_fp8(ctypes.byref(cfg), ctypes.byref(sc), fake, fake, fake, fake, fake, ctypes.byref(f8short), None, None) == -3
+    assert lib.ffn_sparse_backward_fp8(ctypes.byref(cfg), ctypes.byref(sc), fake, fake, fake, None, ctypes.byref(f8good), None, None) == -1
+    assert lib.ffn_sparse_backward_fp8(ctypes.byref(cfg), ctypes.byref(sc), fake, fake, fake, fake, ctypes.byref(f8short), None, None) == -3
+    assert lib.ffn_sparse_forward_fp8_grouped(ctypes.byref(cfg), ctypes.byref(sc), 2, None, fake, fake, fake, fake, fake, ctypes.byref(f8good), None, None) == -1
+    assert lib.ffn_sparse_backward_fp8_grouped(ctypes.byref(cfg), ctypes.byref(sc), 2, None, fake, fake, fake, fake, ctypes.byref(f8good), None, None) == -1
     zero = binding._Fp8Scales(1.0, 1.0, 0.0, 1.0, 1.0, 1.0)
     assert lib.ffn_sparse_step_fp8(ctypes.byref(cfg), ctypes.byref(zero), *args, fake, 1 << 40, None, None) == -1 and b"scales" in lib.sffn_last_error()
     assert lib.sffn_fp8_workspace_bytes(ctypes.byref(cfg)) > 0 and lib.sffn_fp8_workspace_bytes(ctypes.byref(binding._Cfg(512, 192, 1024, 64, 8, 0, 0))) == 0
@@ -170,9 +191,9 @@ def test_workspace_has_no_dense_activation_unless_it_is_stored():
     small, big = sffn.workspace_bytes(T, D, F), sffn.workspace_bytes(T, D, F, keep_dense=True)
     assert big - small == 2 * 2 * T * F
     lay = sffn.workspace_layout(T, D, F)
-    assert lay["y2_vals"] == lay["y1"] and lay["dy1_vals"] == lay["dy2"]            # empty regions
+    assert lay["dy2"] == lay["y1"] == lay["y2_vals"]                                # empty regions
     layk = sffn.workspace_layout(T, D, F, keep_dense=True)
-    assert layk["y2_vals"] - layk["y1"] == 2 * T * F and layk["dy1_vals"] - layk["dy2"] == 2 * T * F
+    assert layk["dy2"] - layk["y1"] == 2 * T * F and layk["y2_vals"] - layk["dy2"] == 2 * T * F
     # blocks of 16 columns: fused like M = 8 when the gathered-row kernel covers the shape (4 F / M a multiple of 64), else / on request unfused
     assert sffn.workspace_bytes(T, D, F, M=16, keep_dense=True) - sffn.workspace_bytes(T, D, F, M=16) == 2 * 2 * T * F
     assert sffn.workspace_bytes(T, D, F, M=16, unfused=True) == sffn.workspace_bytes(T, D, F, M=16, keep_dense=True, unfused=True) > 0

@@ -399,10 +399,14 @@ def test_fp8_forward_and_backward_as_separate_calls_are_bit_identical(M, wgrad_f
     inp = make_ffn_inputs(T, D, F, seed=51)
     dev = {k: to_dev(v) for k, v in inp.items()}
     sc = dict(x=5.0 / 448, w1=0.1 / 448, w2=0.1 / 448, y2=8.0 / 448, dy=5.0 / 448, dy1=2.0 / 448)
-    split = sffn.FfnStepFp8(T, D, F, sc, sffn.MODE_HARD, wgrad_fp8=wgrad_fp8, M=M)
+    sz = sffn.buffer_sizes(T, D, F, sffn.MODE_HARD, M=M, fp8=True, wgrad_fp8=wgrad_fp8)
+    scratch = torch.empty((sz["scratch"],), dtype=torch.uint8, device="cuda")           # a buffer that other layers would use in between
+    split = sffn.FfnStepFp8(T, D, F, sc, sffn.MODE_HARD, wgrad_fp8=wgrad_fp8, M=M, scratch=scratch)
     whole = sffn.FfnStepFp8(T, D, F, sc, sffn.MODE_HARD, wgrad_fp8=wgrad_fp8, M=M)
+    assert sz["scratch"] + sz["saved"] + sz["weights"] == whole.layout["total"]
     split.amax.fill_(-1.0)
     y3 = to_bits(split.forward(dev["X"], dev["W1"], dev["W2"], dev["b1"])).copy()
+    scratch.fill_(0xA5)
     mid = split.amax_dict()
     assert mid["dy"] == -1.0 and mid["dy1"] == -1.0 and mid["x"] > 0 and mid["y2"] > 0       # the forward call leaves the backward pass's maxima alone
     want = [to_bits(t).copy() for t in whole(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]

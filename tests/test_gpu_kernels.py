@@ -787,24 +787,39 @@ def test_grouped_step_on_packed_weights_is_bit_identical():
 
 @pytest.mark.parametrize("M,lean", [(8, False), (8, True), (16, False), (64, True)])
 def test_forward_and_backward_as_separate_calls_are_bit_identical(M, lean):
-    """ffn_sparse_forward (Alg. 1) + ffn_sparse_backward (Alg. 2) against the one-call step; two layers' forward passes run before their backward
-    passes, in the order a training loop has them, so nothing may hide in library state outside each layer's workspace."""
+    """ffn_sparse_forward (Alg. 1) + ffn_sparse_backward (Alg. 2) against the one-call step, in the order a pipelined training loop has them:
+    layer A takes two micro-batches (the second on the weights the first packed: SFFN_FLAG_WEIGHTS_PACKED), layer B one, then the backward
+    passes in reverse.  All three share ONE scratch buffer, filled with garbage between calls; each keeps its own saved buffer; the two
+    micro-batches of layer A share one weights buffer.  Every output must be the bits of a one-call step on a workspace of its own."""
     T, D, F = 320, 256, 1024
-    layers = [make_ffn_inputs(T, D, F, seed=41 + i) for i in range(2)]
-    dev = [{k: to_dev(v) for k, v in inp.items()} for inp in layers]
-    split = [sffn.FfnStep(T, D, F, sffn.MODE_SOFT, M=M, lean=lean) for _ in layers]
-    y3 = [to_bits(st.forward(d["X"], d["W1"], d["W2"], d["b1"])).copy() for st, d in zip(split, dev)]
-    grads = [None, None]
-    for i in (1, 0):
-        grads[i] = [to_bits(t).copy() for t in split[i].backward(dev[i]["W1"], dev[i]["dY"])]
+    wa, wb = make_ffn_inputs(T, D, F, seed=41), make_ffn_inputs(T, D, F, seed=42)
+    mb = [make_ffn_inputs(T, D, F, seed=43 + i) for i in range(2)]                      # layer A's micro-batches: their X and dY
+    cases = [(wa, mb[0]), (wa, mb[1]), (wb, wb)]                                         # (weights and bias of, X and dY of)
+    sz = sffn.buffer_sizes(T, D, F, sffn.MODE_SOFT, M=M, lean=lean)
+    assert sz["scratch"] + sz["saved"] + sz["weights"] == sffn.workspace_bytes(T, D, F, sffn.MODE_SOFT, M=M)
+    scratch = torch.empty((sz["scratch"],), dtype=torch.uint8, device="cuda")
+    a0 = sffn.FfnStep(T, D, F, sffn.MODE_SOFT, M=M, lean=lean, scratch=scratch)
+    a1 = sffn.FfnStep(T, D, F, sffn.MODE_SOFT, M=M, lean=lean, scratch=scratch, weights_of=a0)
+    b0 = sffn.FfnStep(T, D, F, sffn.MODE_SOFT, M=M, lean=lean, scratch=scratch)
+    steps = [a0, a1, b0]
+    with pytest.raises(sffn.SffnError):
+        a0(*[to_dev(wa[k]) for k in ("X", "W1", "W2", "b1", "dY")])                     # the one-call form needs the regions in one piece
+    dev = [dict(X=to_dev(x["X"]), dY=to_dev(x["dY"]), W1=to_dev(w["W1"]), W2=to_dev(w["W2"]), b1=to_dev(w["b1"])) for w, x in cases]
+    y3, grads = [], [None] * 3
+    for i, (st, d) in enumerate(zip(steps, dev)):
+        y3.append(to_bits(st.forward(d["X"], d["W1"], d["W2"], d["b1"], weights_packed=(i == 1))).copy())
+        scratch.fill_(0xA5)
+    for i in (2, 1, 0):
+        grads[i] = [to_bits(t).copy() for t in steps[i].backward(dev[i]["W1"], dev[i]["dY"])]
+        scratch.fill_(0x5A)
     for i, d in enumerate(dev):
         whole = sffn.FfnStep(T, D, F, sffn.MODE_SOFT, M=M, lean=lean)
         want = [to_bits(t).copy() for t in whole(d["X"], d["W1"], d["W2"], d["b1"], d["dY"])]
-        assert np.array_equal(y3[i], want[0]), "Y3"
+        assert np.array_equal(y3[i], want[0]), (i, "Y3")
         for name, x, y in zip(("dX", "dW1", "dW2"), grads[i], want[1:]):
             assert np.array_equal(x, y), (i, name)
-        sa, sb = split[i].saved(), whole.saved()
-        for k in ("y2_meta", "colidx", "y1_kept") + (() if lean else ("y2_vals", "dy1_vals", "w2t_vals")):
+        sa, sb = steps[i].saved(), whole.saved()
+        for k in ("y2_meta", "colidx", "y1_kept") + (() if lean else ("w2t_vals", "w1_meta")):
             assert np.array_equal(to_bits(sa[k]), to_bits(sb[k])), k
 
 
