@@ -298,6 +298,22 @@ int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint1
                          const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX,
                          uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
 
+/* The router's step as two calls (forward: Alg. 1 with Alg. 3 as the sparsifier, eqs. (1)-(3); backward: Alg. 2, eqs. (4)-(8)), for a
+ * training loop in which other layers run in between.  Same launches, order and bits as the one-call forms.  The two halves meet in
+ * `workspace`, which the caller keeps untouched between them (one per layer in flight); the backward call takes the same seg_offsets
+ * and perm as the forward call (ffn_router_full_backward reads the routing that ffn_router_full_forward left in the workspace), and
+ * W1 again: eq. (7) reads the dense W1. */
+int ffn_router_forward(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* X,
+                       const uint16_t* W1, const uint16_t* W2, const float* b1, uint16_t* Y3, void* workspace, size_t ws_bytes,
+                       void* stream);
+int ffn_router_backward(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* W1,
+                        const uint16_t* dY, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes,
+                        void* stream);
+int ffn_router_full_forward(const sffn_cfg* cfg, const uint16_t* means, const uint16_t* X, const uint16_t* W1,
+                            const uint16_t* W2, const float* b1, uint16_t* Y3, void* workspace, size_t ws_bytes, void* stream);
+int ffn_router_full_backward(const sffn_cfg* cfg, const uint16_t* W1, const uint16_t* dY, uint16_t* dX, uint16_t* dW1,
+                             uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
+
 /* Alg. 1 + Alg. 2, one call: X [T,D], W1 [F,D], W2 [D,F], b1 fp32 [F] or NULL, dY [T,D] ->
  * Y3 [T,D], dX [T,D], dW1 [F,D], dW2 [D,F]; intermediates land in `workspace` at the offsets of
  * sffn_workspace_layout().  Both weight matrices are re-pruned inside the call (SFFN_FLAG_WEIGHTS_PACKED: a later micro-batch
@@ -357,8 +373,8 @@ int ffn_sparse_step_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* s
  *   weights  written by a forward call without SFFN_FLAG_WEIGHTS_PACKED (both packed weights, W2.T; fp8: W1's codes too), read by that
  *            call, by its backward call and by every later call with the flag.  One per layer, good until the weights change.
  * The library cannot check what the buffers hold.  Arguments, shapes, alignment, error codes otherwise: those of the one-call entry
- * points (a missing or short buffer: SFFN_EWORKSPACE).  Not built for the unfused wide-block path (SFFN_EUNSUPPORTED) nor for the
- * router's step.  fp8: the forward call writes amax[0..3] (x, w1, w2, y2) and leaves amax[4], amax[5] alone, the backward call writes
+ * points (a missing or short buffer: SFFN_EWORKSPACE).  Not built for the unfused wide-block path (SFFN_EUNSUPPORTED); the router's
+ * step has its own pair, ffn_router_forward / ffn_router_backward.  fp8: the forward call writes amax[0..3] (x, w1, w2, y2) and leaves amax[4], amax[5] alone, the backward call writes
  * amax[4], amax[5] (dy, dy1) only. */
 typedef struct sffn_buffers {
     void*  scratch;  size_t scratch_bytes;

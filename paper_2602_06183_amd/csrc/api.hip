@@ -823,8 +823,11 @@ int sffn_router_workspace_layout(const sffn_cfg* cfg, sffn_router_layout* out) {
 // or as a device array written earlier on the same stream by this library's own grouping kernels (seg_dev).
 static int run_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* seg_dev, const int32_t* perm, const uint16_t* X,
                            const uint16_t* W1, const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX,
-                           uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream, bool check_only = false) {
-    REQUIRE(cfg && (seg_offsets || seg_dev) && perm && X && W1 && W2 && dY && Y3 && dX && dW1 && dW2, SFFN_EINVAL, "ffn_router_step: null pointer");
+                           uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream, bool check_only = false, int phase = 3) {
+    // phase: bit 0 = Alg. 1 with Alg. 3 as the sparsifier (forward pass), bit 1 = Alg. 2 (backward pass); the halves of a split call meet in the workspace
+    const bool fwd = (phase & 1) != 0, bwd = (phase & 2) != 0;
+    REQUIRE(cfg && (seg_offsets || seg_dev) && perm && W1 && (!fwd || (X && W2 && Y3)) && (!bwd || (dY && dX && dW1 && dW2)), SFFN_EINVAL,
+            "ffn_router_step: null pointer");
     REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "ffn_router_step: only V=64 with M in {8, 16, 32, 64} is built");
     RouterLayout L;
     REQUIRE(make_router_layout(cfg, &L), SFFN_EINVAL, "ffn_router_step: T > 0, D and F positive multiples of 64, 4F/M a multiple of 64");
@@ -874,10 +877,10 @@ static int run_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, cons
 
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
     // ---- Alg. 1 with Alg. 3 as the sparsifier ---------------------------------------------------------------------
-    STAGE(launch_transpose(X, rows, D, D, xpt, 0, xb, s, 1, 0, perm), "router/X[perm].T");     // permuted rows: transposed (eq. (8)) and blocked (eq. (1))
-    STAGE(launch_prune24_step(W1, F, D, D, 0, cfg->mode, w1cv, w1cm, w1cvb, w1cmb, nullptr, s, 1, M), "router/prune24(W1)");
-    STAGE(launch_venom_colidx(g1, rows, F / M, colidx, s), "router/colidx");
-    {   // rows past the last run are padding that no contraction writes: one launch clears them in the five row-indexed outputs
+    if (fwd) STAGE(launch_transpose(X, rows, D, D, xpt, 0, xb, s, 1, 0, perm), "router/X[perm].T");     // permuted rows: transposed (eq. (8)) and blocked (eq. (1))
+    if (fwd) STAGE(launch_prune24_step(W1, F, D, D, 0, cfg->mode, w1cv, w1cm, w1cvb, w1cmb, nullptr, s, 1, M), "router/prune24(W1)");
+    if (fwd) STAGE(launch_venom_colidx(g1, rows, F / M, colidx, s), "router/colidx");
+    if (fwd) {   // rows past the last run are padding that no contraction writes: one launch clears them in the five row-indexed outputs
         TailFill tf;
         tf.add(vals, Kc, 0); tf.add(meta, Kc / 8, 0x44); tf.add(y1c, Kc * 2, 0); tf.add(dy2c, Kc * 2, 0); tf.add(dvals, Kc, 0);
         if (seg_dev) LAUNCH(launch_fill_tail_rows(tf, seg_dev + E, 0, rows, 64 * (E + 1), s), "router/clear");      // at most 64 (E + 1) such rows
@@ -886,33 +889,33 @@ static int run_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, cons
     // Inside a run every 64-row block keeps the same columns, so eqs. (3), (7) are plain grouped 2:4 contractions of the
     // packed [rows, Kc] activation with the expert's own [D, Kc] slice of W2 / W1.T (256 x 256 tiles; gathering rows per
     // 64-row block would re-read the same lines from every CU at once)
-    {
+    if (fwd) {
         VnmEpilogue ep;
         ep.mode = 3; ep.store_dense = 1; ep.vals = vals; ep.meta = meta; ep.perm = perm; ep.logM = logM; ep.v24 = avb; ep.m24 = amb;
         STAGE(launch_gemm_vnm_epilogue(w1cvb, w1cmb, xb, b1, Kc, rows, D, y1c, ep, s, &g1), "router/y1c+sqrelu+2:4");    // eqs. (1), (2), Section 2.3
     }
-    STAGE(launch_transpose(W2, D, F, F, w2t, 0, nullptr, s), "router/W2.T");
-    STAGE(launch_transpose(w2t, Kc, D, D, wcb, 1, nullptr, s, E, M), "router/W2[:,e]");
-    STAGE(launch_spmm_blocked(avb, amb, wcb, nullptr, rows, D, Kc, 0, Y3, D, s, &g0), "router/y3");                       // eq. (3)
+    if (fwd) STAGE(launch_transpose(W2, D, F, F, w2t, 0, nullptr, s), "router/W2.T");
+    if (fwd) STAGE(launch_transpose(w2t, Kc, D, D, wcb, 1, nullptr, s, E, M), "router/W2[:,e]");
+    if (fwd) STAGE(launch_spmm_blocked(avb, amb, wcb, nullptr, rows, D, Kc, 0, Y3, D, s, &g0), "router/y3");                       // eq. (3)
     // ---- Alg. 2 ------------------------------------------------------------------------------------------------------
-    STAGE(launch_prune24_step(w2t, F, D, D, 0, cfg->mode, w2cv, w2cm, w2cvb, w2cmb, nullptr, s, 1, M), "router/prune24(W2.T)");
-    STAGE(launch_transpose(dY, rows, D, D, dypt, 0, dyb, s, 1, 0, perm), "router/dY[perm].T");
-    STAGE(launch_venom_expand_t_compact(vals, meta, rows, Kc, at, s), "router/expand(y2)");
+    if (bwd) STAGE(launch_prune24_step(w2t, F, D, D, 0, cfg->mode, w2cv, w2cm, w2cvb, w2cmb, nullptr, s, 1, M), "router/prune24(W2.T)");
+    if (bwd) STAGE(launch_transpose(dY, rows, D, D, dypt, 0, dyb, s, 1, 0, perm), "router/dY[perm].T");
+    if (bwd) STAGE(launch_venom_expand_t_compact(vals, meta, rows, Kc, at, s), "router/expand(y2)");
     // eq. (5) is computed as dW2.T [F, D] (whole 2 D-byte rows per hidden unit) and transposed: writing dW2 [D, F] directly
     // would scatter 8-byte pieces M hidden units apart
-    STAGE(launch_gemm_nt(0, at, nullptr, dypt, nullptr, Kc, D, rows, 0, wcb, D, s, &g2), "router/dW2.T");                 // eq. (5)
-    STAGE(launch_transpose(wcb, F, D, D, dW2, 0, nullptr, s), "router/dW2");
-    {   // eq. (4) at the expert's hidden units, then eq. (6) on y2's slots while the tile is in LDS; dy2c itself only on request
+    if (bwd) STAGE(launch_gemm_nt(0, at, nullptr, dypt, nullptr, Kc, D, rows, 0, wcb, D, s, &g2), "router/dW2.T");                 // eq. (5)
+    if (bwd) STAGE(launch_transpose(wcb, F, D, D, dW2, 0, nullptr, s), "router/dW2");
+    if (bwd) {   // eq. (4) at the expert's hidden units, then eq. (6) on y2's slots while the tile is in LDS; dy2c itself only on request
         GemmGroup g4 = g1;
         g4.bias_stride = 0;
         VnmEpilogue ep;
         ep.mode = 4; ep.store_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0; ep.vals = dvals; ep.meta = meta; ep.ykept = y1c; ep.v24 = avb;
         STAGE(launch_gemm_vnm_epilogue(w2cvb, w2cmb, dyb, nullptr, Kc, rows, D, dy2c, ep, s, &g4), "router/dy2c+dsqrelu");
     }
-    STAGE(launch_transpose(W1, Kc, D, D, wcb, 1, nullptr, s, E, M), "router/W1[e].T");
-    STAGE(launch_spmm_blocked(avb, amb, wcb, nullptr, rows, D, Kc, 0, dX, D, s, &g0), "router/dX");                       // eq. (7)
-    STAGE(launch_venom_expand_t_compact(dvals, meta, rows, Kc, at, s), "router/expand(dy1)");
-    STAGE(launch_gemm_nt(0, at, nullptr, xpt, nullptr, Kc, D, rows, 0, dW1, D, s, &g2), "router/dW1");                    // eq. (8)
+    if (bwd) STAGE(launch_transpose(W1, Kc, D, D, wcb, 1, nullptr, s, E, M), "router/W1[e].T");
+    if (bwd) STAGE(launch_spmm_blocked(avb, amb, wcb, nullptr, rows, D, Kc, 0, dX, D, s, &g0), "router/dX");                       // eq. (7)
+    if (bwd) STAGE(launch_venom_expand_t_compact(dvals, meta, rows, Kc, at, s), "router/expand(dy1)");
+    if (bwd) STAGE(launch_gemm_nt(0, at, nullptr, xpt, nullptr, Kc, D, rows, 0, dW1, D, s, &g2), "router/dW1");                    // eq. (8)
     return SFFN_OK;
 }
 
@@ -921,6 +924,18 @@ int ffn_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32
                     uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
     REQUIRE(seg_offsets, SFFN_EINVAL, "ffn_router_step: null pointer");
     return run_router_step(cfg, seg_offsets, nullptr, perm, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, ws_bytes, stream);
+}
+
+// Alg. 1 (with Alg. 3 as the sparsifier) and Alg. 2 of the router's step as separate calls on one workspace
+int ffn_router_forward(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* X, const uint16_t* W1,
+                       const uint16_t* W2, const float* b1, uint16_t* Y3, void* workspace, size_t ws_bytes, void* stream) {
+    REQUIRE(seg_offsets, SFFN_EINVAL, "ffn_router_forward: null pointer");
+    return run_router_step(cfg, seg_offsets, nullptr, perm, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, workspace, ws_bytes, stream, false, 1);
+}
+int ffn_router_backward(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* W1, const uint16_t* dY,
+                        uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
+    REQUIRE(seg_offsets, SFFN_EINVAL, "ffn_router_backward: null pointer");
+    return run_router_step(cfg, seg_offsets, nullptr, perm, nullptr, W1, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, stream, false, 2);
 }
 
 // Routing buffers of ffn_router_full_step, behind the step's own workspace: expert [T], perm [rows], row_of_token [T],
@@ -946,10 +961,11 @@ size_t sffn_router_full_workspace_bytes(const sffn_cfg* cfg) {
     return A.total;
 }
 
-int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint16_t* X, const uint16_t* W1, const uint16_t* W2,
-                         const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace,
-                         size_t ws_bytes, void* stream) {
-    REQUIRE(cfg && means && X && workspace, SFFN_EINVAL, "ffn_router_full_step: null pointer");
+namespace {
+int run_router_full(const sffn_cfg* cfg, const uint16_t* means, const uint16_t* X, const uint16_t* W1, const uint16_t* W2,
+                    const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace,
+                    size_t ws_bytes, void* stream, int phase) {
+    REQUIRE(cfg && (!(phase & 1) || (means && X)) && workspace, SFFN_EINVAL, "ffn_router_full_step: null pointer");
     REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "ffn_router_full_step: only V=64 with M in {8, 16, 32, 64} is built");
     RouterLayout L;
     RouteArea A;
@@ -962,13 +978,30 @@ int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint1
     int32_t* perm = (int32_t*)(ws + A.perm);
     int32_t* seg = (int32_t*)(ws + A.seg);
     // the step's own argument checks run first, so that a rejected call leaves nothing on the stream
-    const int pre = run_router_step(cfg, nullptr, seg, perm, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, L.total, stream, true);
+    const int pre = run_router_step(cfg, nullptr, seg, perm, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, L.total, stream, true, phase);
     if (pre != SFFN_OK) return pre;
-    const int rc = venom_route(X, means, cfg->T, cfg->D, cfg->M, expert, perm, (int32_t*)(ws + A.row_of_token), seg, nullptr, ws + A.counts,
-                               A.total - A.counts, stream);
-    if (rc != SFFN_OK) return rc;
+    if (phase & 1) {        // the backward half of a split call reads the routing its forward half left in the workspace
+        const int rc = venom_route(X, means, cfg->T, cfg->D, cfg->M, expert, perm, (int32_t*)(ws + A.row_of_token), seg, nullptr, ws + A.counts,
+                                   A.total - A.counts, stream);
+        if (rc != SFFN_OK) return rc;
+    }
     // the run offsets stay on the device: no read-back, the grouped launches are sized for the worst case
-    return run_router_step(cfg, nullptr, seg, perm, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, L.total, stream);
+    return run_router_step(cfg, nullptr, seg, perm, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, L.total, stream, false, phase);
+}
+}  // namespace
+
+int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint16_t* X, const uint16_t* W1, const uint16_t* W2,
+                         const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace,
+                         size_t ws_bytes, void* stream) {
+    return run_router_full(cfg, means, X, W1, W2, b1, dY, Y3, dX, dW1, dW2, workspace, ws_bytes, stream, 3);
+}
+int ffn_router_full_forward(const sffn_cfg* cfg, const uint16_t* means, const uint16_t* X, const uint16_t* W1, const uint16_t* W2,
+                            const float* b1, uint16_t* Y3, void* workspace, size_t ws_bytes, void* stream) {
+    return run_router_full(cfg, means, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, workspace, ws_bytes, stream, 1);
+}
+int ffn_router_full_backward(const sffn_cfg* cfg, const uint16_t* W1, const uint16_t* dY, uint16_t* dX, uint16_t* dW1, uint16_t* dW2,
+                             void* workspace, size_t ws_bytes, void* stream) {
+    return run_router_full(cfg, nullptr, nullptr, W1, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, stream, 2);
 }
 
 // Alg. 1 + Alg. 2 for n_experts independent FFNs over consecutive token segments (n_experts = 1, seg = nullptr:

@@ -182,6 +182,16 @@ def test_router_entry_points_validate_on_the_host():
     assert lib.ffn_router_full_step(ctypes.byref(cfg), *args, fake, 16, None) == -3
     assert lib.ffn_router_full_step(ctypes.byref(cfg), None, *args[1:], fake, big, None) == -1
     assert lib.ffn_router_full_step(ctypes.byref(m12), *args, fake, big, None) == -2
+    # the router's step as two calls: each half checks what it reads
+    assert lib.ffn_router_forward(ctypes.byref(cfg), ok, fake, fake, fake, fake, fake, fake, fake, 16, None) == -3
+    assert lib.ffn_router_forward(ctypes.byref(cfg), ok, fake, None, fake, fake, fake, fake, fake, big, None) == -1
+    assert lib.ffn_router_backward(ctypes.byref(cfg), ok, fake, fake, None, fake, fake, fake, fake, big, None) == -1
+    assert lib.ffn_router_backward(ctypes.byref(cfg), None, fake, fake, fake, fake, fake, fake, fake, big, None) == -1
+    assert lib.ffn_router_backward(ctypes.byref(m12), ok, fake, fake, fake, fake, fake, fake, fake, big, None) == -2
+    assert lib.ffn_router_full_forward(ctypes.byref(cfg), None, fake, fake, fake, fake, fake, fake, big, None) == -1
+    assert lib.ffn_router_full_forward(ctypes.byref(cfg), fake, fake, fake, fake, fake, fake, fake, 16, None) == -3
+    assert lib.ffn_router_full_backward(ctypes.byref(cfg), fake, None, fake, fake, fake, fake, big, None) == -1
+    assert lib.ffn_router_full_backward(ctypes.byref(cfg), fake, fake, fake, fake, fake, fake, 16, None) == -3
 
 
 def test_workspace_has_no_dense_activation_unless_it_is_stored():

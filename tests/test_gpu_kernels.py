@@ -664,6 +664,15 @@ def test_ffn_router_step_against_oracle(M, mode, T, D, F):
     sv_one = {k: to_bits(v) for k, v in one.saved().items()}
     assert all(np.array_equal(a, b) for a, b in zip(outs_one, (Y3, dX, dW1, dW2)))
     assert all(np.array_equal(sv_one[k], sv[k]) for k in ("y1c", "vals", "meta", "colidx", "dvals"))
+    # forward and backward as separate calls, another layer's step in between: the same bits again, in both forms
+    two, two_full = sffn.FfnRouterStep(T, D, F, M, mode), sffn.FfnRouterStep(T, D, F, M, mode)
+    y3_a = to_bits(two.forward(route, dev["X"], dev["W1"], dev["W2"], dev["b1"])).copy()
+    y3_b = to_bits(two_full.full_forward(dev["means"], dev["X"], dev["W1"], dev["W2"], dev["b1"])).copy()
+    one.full(dev["means"], torch.flip(dev["X"], (0,)).contiguous(), dev["W1"], dev["W2"], dev["b1"], dev["dY"])
+    g_b = [to_bits(t).copy() for t in two_full.full_backward(dev["W1"], dev["dY"])]
+    g_a = [to_bits(t).copy() for t in two.backward(route, dev["W1"], dev["dY"])]
+    assert np.array_equal(y3_a, Y3) and np.array_equal(y3_b, Y3)
+    assert all(np.array_equal(a, b) for a, b in zip(g_a, (dX, dW1, dW2))) and all(np.array_equal(a, b) for a, b in zip(g_b, (dX, dW1, dW2)))
     expert = oracle.route_top1(oracle.route_scores(inp["X"], inp["means"]))
     perm, seg = oracle.expert_permutation(expert, M // 4)
     assert np.array_equal(to_bits(route["perm"]), perm) and route["seg"] == [int(v) for v in seg]
