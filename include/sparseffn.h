@@ -74,6 +74,7 @@ typedef struct sffn_cfg {
  * y2_vals and dy1_vals of sffn_ws_layout (at M >= 16 eqs. (3), (7) read those two).  They are inspection aids: every consumer inside the
  * step reads its own operand layouts, and Y3, dX, dW1, dW2, y2_meta, colidx, y1_kept are the same bits with or without the flag.  Ignored
  * by the unfused path. */
+/* (With the flag those regions of the workspace are empty, 0 bytes: sffn_workspace_bytes() and the layouts depend on it.) */
 #define SFFN_FLAG_LEAN 8
 /* ffn_sparse_step, ffn_sparse_step_grouped, ffn_sparse_step_fp8, ffn_sparse_step_fp8_grouped (not the unfused path, not the router
  * steps: SFFN_EUNSUPPORTED there): the weights are already packed.  Section 3.4 notes that the conversion of a weight to 2:4 is paid

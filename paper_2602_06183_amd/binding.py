@@ -264,6 +264,13 @@ class _StepBuffers:
             raise SffnError("this step object was built on a shared scratch buffer: use forward() / backward()")
         return _ptr(self.ws)
 
+    def _drop_unwritten(self, out, M, weight_keys, activation_keys):
+        """SFFN_FLAG_LEAN: the canonical copies that are not written have no room in the layout either."""
+        if getattr(self, "lean", False):
+            for k in weight_keys + (activation_keys if M == 8 else ()):
+                out.pop(k, None)
+        return out
+
     def _region_bytes(self, off, nbytes):
         """nbytes at layout offset `off`, wherever its region lives."""
         if off < self._b1:
@@ -293,13 +300,13 @@ def _flags(keep_dense, unfused=False, lean=False):
     return (FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_UNFUSED if unfused else 0) | (FLAG_LEAN if lean else 0)
 
 
-def workspace_bytes(T, D, F, mode=MODE_HARD, M=8, keep_dense=False, unfused=False):
-    c = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused))
+def workspace_bytes(T, D, F, mode=MODE_HARD, M=8, keep_dense=False, unfused=False, lean=False):
+    c = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused, lean))
     return load().sffn_workspace_bytes(ctypes.byref(c))
 
 
-def workspace_layout(T, D, F, mode=MODE_HARD, M=8, keep_dense=False, unfused=False):
-    c, lay = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused)), _Layout()
+def workspace_layout(T, D, F, mode=MODE_HARD, M=8, keep_dense=False, unfused=False, lean=False):
+    c, lay = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused, lean)), _Layout()
     _check(load().sffn_workspace_layout(ctypes.byref(c), ctypes.byref(lay)))
     return {n: getattr(lay, n) for n, _ in _Layout._fields_}
 
@@ -440,7 +447,8 @@ class FfnStep(_StepBuffers):
         configuration whose weights region this object shares (a second micro-batch of one layer)."""
         self.T, self.D, self.F, self.mode, self.keep_dense, self.M = T, D, F, mode, keep_dense, M
         self.cfg = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused, lean))
-        self.layout = workspace_layout(T, D, F, mode, M, keep_dense, unfused)
+        self.layout = workspace_layout(T, D, F, mode, M, keep_dense, unfused, lean)
+        self.lean = lean and self.layout["w1_meta"] == self.layout["w1_vals"]       # (the unfused path ignores the flag)
         assert self._alloc_regions(load().sffn_buffer_sizes, 1, device, scratch, weights_of) == self.layout["total"]
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
         self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
@@ -496,7 +504,7 @@ class FfnStep(_StepBuffers):
             out["y1"], out["dy2"] = view(L["y1"], (T, F), torch.bfloat16), view(L["dy2"], (T, F), torch.bfloat16)
         if L["y1_kept_bytes"]:
             out["y1_kept"] = view(L["y1_kept"], (T, 2 * F // M), torch.bfloat16)
-        return out
+        return self._drop_unwritten(out, self.M, ('w1_vals', 'w1_meta', 'w2t_vals', 'w2t_meta'), ('y2_vals', 'dy1_vals'))
 
 
 class FfnStepGrouped(_StepBuffers):
@@ -511,6 +519,7 @@ class FfnStepGrouped(_StepBuffers):
         lay = _Layout()
         _check(load().sffn_grouped_workspace_layout(ctypes.byref(self.cfg), self.E, ctypes.byref(lay)))
         self.layout = {n: getattr(lay, n) for n, _ in _Layout._fields_}
+        self.lean = lean and self.layout["w1_meta"] == self.layout["w1_vals"]
         assert self._alloc_regions(load().sffn_buffer_sizes, self.E, device, scratch) == self.layout["total"]
         self.Y3, self.dX = _bf16((self.T, D), device), _bf16((self.T, D), device)
         self.dW1, self.dW2 = _bf16((self.E, F, D), device), _bf16((self.E, D, F), device)
@@ -565,7 +574,7 @@ class FfnStepGrouped(_StepBuffers):
                    y1_kept=view(L["y1_kept"], (T, 2 * F // M), torch.bfloat16))
         if self.keep_dense:
             out["y1"], out["dy2"] = view(L["y1"], (T, F), torch.bfloat16), view(L["dy2"], (T, F), torch.bfloat16)
-        return out
+        return self._drop_unwritten(out, self.M, ('w1_vals', 'w1_meta', 'w2t_vals', 'w2t_meta'), ('y2_vals', 'dy1_vals'))
 
 
 def ffn_sparse_step(X, W1, W2, b1, dY, mode=MODE_HARD, keep_dense=True, M=8, unfused=False):
@@ -657,6 +666,7 @@ class FfnStepFp8(_StepBuffers):
         _check(load().sffn_fp8_workspace_layout(ctypes.byref(self.cfg), ctypes.byref(lay)))
         self.layout = {n: getattr(lay, n) for n, _ in _Fp8Layout._fields_}
         self.keep_dense = keep_dense
+        self.lean = lean
         assert self._alloc_regions(load().sffn_fp8_buffer_sizes, 1, device, scratch) == self.layout["total"]
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
         self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
@@ -723,7 +733,7 @@ class FfnStepFp8(_StepBuffers):
             out["dy1_codes"] = view(L["dy1_vals"], (T, 2 * F // M), u8)
         if self.keep_dense:
             out["y1"], out["dy2"] = view(L["y1"], (T, F), torch.bfloat16), view(L["dy2"], (T, F), torch.bfloat16)
-        return out
+        return self._drop_unwritten(out, self.M, ('w1_codes', 'w1_meta', 'w2t_codes', 'w2t_meta'), ('y2_codes',))
 
 
 class FfnStepFp8Grouped(FfnStepFp8):
@@ -738,6 +748,7 @@ class FfnStepFp8Grouped(FfnStepFp8):
         lay = _Fp8Layout()
         _check(load().sffn_fp8_grouped_workspace_layout(ctypes.byref(self.cfg), self.E, ctypes.byref(lay)))
         self.layout = {n: getattr(lay, n) for n, _ in _Fp8Layout._fields_}
+        self.lean = lean
         assert self._alloc_regions(load().sffn_fp8_buffer_sizes, self.E, device, scratch) == self.layout["total"]
         self.Y3, self.dX = _bf16((self.T, D), device), _bf16((self.T, D), device)
         self.dW1, self.dW2 = _bf16((self.E, F, D), device), _bf16((self.E, D, F), device)
@@ -796,7 +807,7 @@ class FfnStepFp8Grouped(FfnStepFp8):
             out["dy1_codes"] = view(L["dy1_vals"], (T, 2 * F // M), u8)
         if self.keep_dense:
             out["y1"], out["dy2"] = view(L["y1"], (T, F), torch.bfloat16), view(L["dy2"], (T, F), torch.bfloat16)
-        return out
+        return self._drop_unwritten(out, self.M, ('w1_codes', 'w1_meta', 'w2t_codes', 'w2t_meta'), ('y2_codes',))
 
 
 NOALLOC_WORKSPACE_MAX = 32 << 20

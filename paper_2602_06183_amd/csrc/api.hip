@@ -88,6 +88,7 @@ bool make_layout(const sffn_cfg* c, FullLayout* L, int n_experts = 1) {
     // the dense y1 / dy2 exist only where a kernel stores them: on request in the fused step, always in the unfused one
     const bool fused = M == 8 || fused_wide(c);
     const bool dense = (c->flags & SFFN_FLAG_KEEP_DENSE) || !fused;
+    const bool lean = fused && (c->flags & SFFN_FLAG_LEAN);          // canonical copies that are not written take no room
     const size_t T = c->T, D = c->D, F = (size_t)c->F * n_experts;   // F only sizes weight-shaped tensors below ...
     const size_t TF = T * (size_t)c->F;                               // ... token x hidden tensors use TF
     size_t off = 0;
@@ -95,8 +96,8 @@ bool make_layout(const sffn_cfg* c, FullLayout* L, int n_experts = 1) {
     // ---- scratch -----------------------------------------------------------------------------------------------------------------------
     L->pub.y1 = take(dense ? TF * 2 : 0);
     L->pub.dy2 = take(dense ? TF * 2 : 0);
-    L->pub.y2_vals = take(TF * 4 / M);
-    L->pub.dy1_vals = take(TF * 4 / M);
+    L->pub.y2_vals = take(lean && M == 8 ? 0 : TF * 4 / M);        // (M >= 16: eqs. (3), (7) read the canonical arrays)
+    L->pub.dy1_vals = take(lean && M == 8 ? 0 : TF * 4 / M);
     L->x_blk = take(T * D * 2);
     L->dy_blk = take(T * D * 2);           L->dyt_blk = take(D * T * 2);
     L->a24_vblk = take(TF);             // M = 8: the survivors in the V:2:8 kernel's units; unfused path: the plain-2:4 view
@@ -112,8 +113,8 @@ bool make_layout(const sffn_cfg* c, FullLayout* L, int n_experts = 1) {
     L->kmask = take(TF / 64 / 8);       // kept-column bit mask per (64-token block, group of 8 hidden units)
     L->saved_end = off;
     // ---- weights -----------------------------------------------------------------------------------------------------------------------
-    L->pub.w1_vals = take(F * D);          L->pub.w1_meta = take(F * D / 8);
-    L->pub.w2t_vals = take(F * D);         L->pub.w2t_meta = take(F * D / 8);
+    L->pub.w1_vals = take(lean ? 0 : F * D);          L->pub.w1_meta = take(lean ? 0 : F * D / 8);
+    L->pub.w2t_vals = take(lean ? 0 : F * D);         L->pub.w2t_meta = take(lean ? 0 : F * D / 8);
     L->w1_vblk = take(F * D);              L->w1_mblk = take(F * D / 8);
     L->w2t_vblk = take(F * D);             L->w2t_mblk = take(F * D / 8);
     L->w2_blk = take(fused ? D * F * 2 : 0);       // fused paths: W2.T [F, D] per expert, written by the pruning pass of W2
@@ -462,13 +463,14 @@ bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L, int n_experts = 1) {
     if (c->M != 8 && !(vnm_ok(c->V, c->M) && vnm_spmm_gather_fp8_ok(c->T, c->D, c->F, c->M))) return false;
     if (c->flags & ~(SFFN_FLAG_KEEP_DENSE | SFFN_FLAG_FP8_WGRAD | SFFN_FLAG_LEAN | SFFN_FLAG_WEIGHTS_PACKED)) return false;
     const bool dense = (c->flags & SFFN_FLAG_KEEP_DENSE) != 0;
+    const bool lean = (c->flags & SFFN_FLAG_LEAN) != 0;              // canonical copies that are not written take no room
     const size_t T = c->T, D = c->D, F = (size_t)c->F * n_experts, TF = T * (size_t)c->F, M = (size_t)c->M;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
     // ---- scratch -----------------------------------------------------------------------------------------------------------------------
     L->pub.y1 = take(dense ? TF * 2 : 0);
     L->pub.dy2 = take(dense ? TF * 2 : 0);
-    L->pub.y2_codes = take(2 * TF / M);
+    L->pub.y2_codes = take(lean && M == 8 ? 0 : 2 * TF / M);        // (M >= 16: eq. (3) reads the canonical codes)
     L->pub.dy1_vals = take(M == 8 ? TF / 2 : 2 * TF / M);
     L->xq = take(T * D);                   L->dyq = take(T * D);
     L->dyt_blk = take(T * D * 2);
@@ -483,8 +485,8 @@ bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L, int n_experts = 1) {
     L->at_blk = take(TF);                  L->kmask = take(TF / 64 / 8);
     L->saved_end = off;
     // ---- weights (what the two weight passes write; eq. (7) reads W1's codes from here) ---------------------------------------------------
-    L->pub.w1_codes = take(F * D / 2);     L->pub.w1_meta = take(F * D / 8);
-    L->pub.w2t_codes = take(F * D / 2);    L->pub.w2t_meta = take(F * D / 8);
+    L->pub.w1_codes = take(lean ? 0 : F * D / 2);     L->pub.w1_meta = take(lean ? 0 : F * D / 8);
+    L->pub.w2t_codes = take(lean ? 0 : F * D / 2);    L->pub.w2t_meta = take(lean ? 0 : F * D / 8);
     L->w1_blk = take(F * D / 2);           L->w2t_blk = take(F * D / 2);
     L->w1_mblk = take(F * D / 8);          L->w2t_mblk = take(F * D / 8);
     L->w2q = take(D * F);                  L->w1tq = take(D * F);

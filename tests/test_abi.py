@@ -194,6 +194,15 @@ def test_router_entry_points_validate_on_the_host():
     assert lib.ffn_router_full_backward(ctypes.byref(cfg), fake, fake, fake, fake, fake, fake, 16, None) == -3
 
 
+def test_lean_workspace_has_no_room_for_the_copies_it_does_not_write():
+    T, D, F = 512, 256, 1024
+    assert sffn.workspace_bytes(T, D, F) - sffn.workspace_bytes(T, D, F, lean=True) == 2 * F * D + 2 * (F * D // 8) + 2 * (T * F // 2)
+    assert sffn.workspace_bytes(T, D, F, M=16) - sffn.workspace_bytes(T, D, F, M=16, lean=True) == 2 * F * D + 2 * (F * D // 8)    # eqs. (3), (7) read the packed activations
+    assert sffn.workspace_bytes(T, D, F, M=16, unfused=True) == sffn.workspace_bytes(T, D, F, M=16, unfused=True, lean=True)        # the unfused path ignores the flag
+    lay = sffn.workspace_layout(T, D, F, lean=True)
+    assert lay["w1_vals"] == lay["w1_meta"] == lay["w2t_vals"] == lay["w2t_meta"]                                                   # empty regions
+
+
 def test_workspace_has_no_dense_activation_unless_it_is_stored():
     """Without SFFN_FLAG_KEEP_DENSE the fused M = 8 step never writes the dense y1 / dy2, and its workspace has no room for
     them: exactly 2 x 2 T F bytes smaller.  The unfused wide-block path always stores them.  Unknown M: no layout."""
