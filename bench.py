@@ -67,14 +67,17 @@ def main():
                     help="V:2:M block width of the activation format (Table 5); 8 is the headline configuration")
     ap.add_argument("--router", action="store_true",
                     help="time the neuron-level router's training step (Section 3.3: ffn_router_full_step = routing + grouped step, M / 4 experts) instead of the magnitude-based V:N:M step")
-    ap.add_argument("--settle-s", type=float, default=10.0,
-                    help="seconds of untimed work (both steps alternating) before the warm-up, so that the timed region sees steady-state clocks")
+    ap.add_argument("--settle-s", type=float, default=None,
+                    help="seconds of untimed work (both steps alternating) before the warm-up, so that the timed region sees steady-state clocks "
+                         "(default 10; 0 with --headline-only, whose runs are traced by a profiler)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--headline-only", action="store_true", help="skip the other configurations, the stand-alone kernels and the micro-benchmarks (profiling runs)")
     ap.add_argument("--fp8", action="store_true", help="with --headline-only: also run the fp8 step (both weight-gradient variants) at the headline shape (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference kernel for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
+    if args.settle_s is None:
+        args.settle_s = 0.0 if args.headline_only else 10.0
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the step shards by tokens; no multi-GPU path is built). Use --gpus 1.")
 
