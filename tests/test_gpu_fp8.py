@@ -422,8 +422,12 @@ def test_fp8_grouped_forward_and_backward_as_separate_calls_are_bit_identical():
     m = make_moe_inputs(n_tokens=700, n_experts=3, top_k=2, D=D, F=F, seed=6)
     dev = {k: to_dev(m[k]) for k in ("X", "W1", "W2", "b1", "dY")}
     sc = dict(x=5.0 / 448, w1=0.1 / 448, w2=0.1 / 448, y2=8.0 / 448, dy=5.0 / 448, dy1=2.0 / 448)
-    split, whole = sffn.FfnStepFp8Grouped(m["seg"], D, F, sc, wgrad_fp8=True), sffn.FfnStepFp8Grouped(m["seg"], D, F, sc, wgrad_fp8=True)
+    sz = sffn.buffer_sizes(int(m["seg"][-1]), D, F, n_experts=3, fp8=True, wgrad_fp8=True)
+    scratch = torch.empty((sz["scratch"],), dtype=torch.uint8, device="cuda")
+    split, whole = sffn.FfnStepFp8Grouped(m["seg"], D, F, sc, wgrad_fp8=True, scratch=scratch), sffn.FfnStepFp8Grouped(m["seg"], D, F, sc, wgrad_fp8=True)
+    assert sz["scratch"] + sz["saved"] + sz["weights"] == whole.layout["total"]
     y3 = to_bits(split.forward(dev["X"], dev["W1"], dev["W2"], dev["b1"])).copy()
+    scratch.fill_(0x5A)
     want = [to_bits(t).copy() for t in whole(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
     got = [y3] + [to_bits(t).copy() for t in split.backward(dev["dY"])]
     for name, x, y in zip(("Y3", "dX", "dW1", "dW2"), got, want):

@@ -838,9 +838,13 @@ def test_grouped_forward_and_backward_as_separate_calls_are_bit_identical():
     D, F = 192, 320
     m = make_moe_inputs(n_tokens=900, n_experts=4, top_k=2, D=D, F=F, seed=5)
     dev = {k: to_dev(m[k]) for k in ("X", "W1", "W2", "b1", "dY")}
-    split, whole = sffn.FfnStepGrouped(m["seg"], D, F), sffn.FfnStepGrouped(m["seg"], D, F)
+    sz = sffn.buffer_sizes(int(m["seg"][-1]), D, F, n_experts=4)
+    scratch = torch.empty((sz["scratch"],), dtype=torch.uint8, device="cuda")
+    split, whole = sffn.FfnStepGrouped(m["seg"], D, F, scratch=scratch), sffn.FfnStepGrouped(m["seg"], D, F)
+    assert sz["scratch"] + sz["saved"] + sz["weights"] == whole.layout["total"]
     y3 = to_bits(split.forward(dev["X"], dev["W1"], dev["W2"], dev["b1"])).copy()
     whole(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])                             # another layer's work in between
+    scratch.fill_(0xA5)
     got = [y3] + [to_bits(t).copy() for t in split.backward(dev["W1"], dev["dY"])]
     want = [to_bits(t).copy() for t in (whole.Y3, whole.dX, whole.dW1, whole.dW2)]
     for name, x, y in zip(("Y3", "dX", "dW1", "dW2"), got, want):
