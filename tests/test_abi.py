@@ -303,3 +303,54 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_HERE", str(tmp_path))
     with pytest.raises(sffn.SffnError):
         binding.load()
+
+
+def test_workspace_layout_properties_over_random_configurations():
+    """Host logic of the layouts, for shapes and flags drawn at random: the public regions are 256-byte aligned, disjoint, large enough for
+    what the header says they hold and inside the workspace; the three buffers of the split calls add up to it; SFFN_FLAG_KEEP_DENSE only
+    adds the two dense activations and SFFN_FLAG_LEAN only removes the copies it does not write; the grouped layout scales the
+    weight-shaped regions by the number of experts and nothing else."""
+    from hypothesis import given, settings, strategies as st
+    lib = sffn.load()
+
+    def regions(T, D, F, M, flags, E=1):
+        c, lay, buf = binding._Cfg(T, D, F, 64, M, 0, flags), binding._Layout(), binding._Buffers()
+        assert lib.sffn_grouped_workspace_layout(ctypes.byref(c), E, ctypes.byref(lay)) == 0
+        assert lib.sffn_buffer_sizes(ctypes.byref(c), E, ctypes.byref(buf)) == 0
+        return {n: getattr(lay, n) for n, _ in binding._Layout._fields_}, buf
+
+    @settings(max_examples=150, deadline=None)
+    @given(st.integers(1, 40), st.integers(1, 12), st.integers(1, 24), st.sampled_from([8, 16, 32, 64]), st.sampled_from([0, 1, 2, 8, 9, 10]),
+           st.integers(1, 5))
+    def check(t, d, f, M, flags, E):
+        T, D, F = 64 * t, 64 * d, 2 * M * f
+        if F % 64:
+            return
+        lay, buf = regions(T, D, F, M, flags, E)
+        assert buf.scratch_bytes + buf.saved_bytes + buf.weights_bytes == lay["total"]
+        fused = M == 8 or (not (flags & 2) and (4 * F // M) % 64 == 0 and 4 * F // M <= 7168)
+        dense, lean = bool(flags & 1) or not fused, bool(flags & 8) and fused
+        need = dict(w1_vals=0 if lean else E * F * D, w1_meta=0 if lean else E * F * D // 8, w2t_vals=0 if lean else E * F * D,
+                    w2t_meta=0 if lean else E * F * D // 8, y1=2 * T * F if dense else 0, dy2=2 * T * F if dense else 0,
+                    y2_vals=0 if (lean and M == 8) else 4 * T * F // M, dy1_vals=0 if (lean and M == 8) else 4 * T * F // M,
+                    y2_meta=T * F // (2 * M), colidx=T // 64 * (F // M) * 4, y1_kept=4 * T * F // M if fused else 0)
+        assert lay["y1_kept_bytes"] == need["y1_kept"]
+        spans = sorted((lay[k], lay[k] + need[k]) for k in need)
+        for (a0, a1), (b0, b1) in zip(spans, spans[1:]):
+            assert a1 <= b0                                            # disjoint
+        assert all(lay[k] % 256 == 0 for k in need) and spans[-1][1] <= lay["total"]
+        # which buffer a region lands in: scratch, saved, weights, in this order of offsets
+        b1_, b2_ = buf.scratch_bytes, buf.scratch_bytes + buf.saved_bytes
+        for k in ("y1", "dy2", "y2_vals", "dy1_vals"):
+            assert lay[k] + need[k] <= b1_
+        for k in ("y2_meta", "colidx", "y1_kept"):
+            assert b1_ <= lay[k] and lay[k] + need[k] <= b2_
+        for k in ("w1_vals", "w1_meta", "w2t_vals", "w2t_meta"):
+            assert b2_ <= lay[k]
+        if fused:
+            more, _ = regions(T, D, F, M, flags | 1, E)
+            less, _ = regions(T, D, F, M, flags | 8, E)
+            assert more["total"] - lay["total"] == (0 if dense else 2 * 2 * T * F)
+            assert lay["total"] - less["total"] == (0 if lean else 2 * E * F * D + 2 * (E * F * D // 8) + (2 * (4 * T * F // M) if M == 8 else 0))
+
+    check()
