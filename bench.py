@@ -431,7 +431,25 @@ def main():
                 run_b = lambda: hw.step.backward(hw.W1, hw.dY)
                 run_f(); run_b()
                 split_ms = {"forward_ms": round(timed(run_f, esteps), 4), "backward_ms": round(timed(run_b, esteps), 4)}
+            accum = None
+            if not hw.moe:      # weight gradients summed over the micro-batches in float32: inside the weight-gradient GEMMs' epilogues
+                                # (SFFN_FLAG_DW_FP32_ACCUMULATE) against bf16 outputs + one add pass per weight in the framework
+                acc_step = sffn.FfnStep(hw.T, hw.D, hw.F, mode, M=M, lean=True, dw_fp32=True)
+                main1, main2 = torch.zeros_like(acc_step.dW1), torch.zeros_like(acc_step.dW2)
+                run_fused = lambda: acc_step(hw.X, hw.W1, hw.W2, hw.b1, hw.dY, weights_packed=True)
+
+                def run_separate():
+                    _, _, g1, g2 = hw.step(hw.X, hw.W1, hw.W2, hw.b1, hw.dY, weights_packed=True)
+                    main1.add_(g1)
+                    main2.add_(g2)
+                acc_step(hw.X, hw.W1, hw.W2, hw.b1, hw.dY)
+                run_fused(); run_separate()
+                accum = {"fused_into_the_weight_gradient_gemms_ms": round(timed(run_fused, esteps), 4),
+                         "bf16_outputs_plus_add_passes_ms": round(timed(run_separate, esteps), 4)}
+                del acc_step, main1, main2
+                free()
             micro = {"weights_packed_ms_per_micro_batch": round(ms_p, 4), "speedup_vs_dense": round(de_h / ms_p, 4), "separate_calls": split_ms,
+                     "float32_gradient_accumulation": accum,
                      "four_micro_batches_per_optimizer_step": {"ms_per_micro_batch": round((sp_h + 3 * ms_p) / 4, 4),
                                                                "speedup_vs_dense": round(de_h / ((sp_h + 3 * ms_p) / 4), 4)}}
         fp8_step = fp8_section(hw, esteps, ewarm, 0.5 * (res["ms_sparse"] + res["ms_sparse2"]), 0.5 * (res["ms_dense"] + res["ms_dense2"]))

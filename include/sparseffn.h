@@ -84,6 +84,12 @@ typedef struct sffn_cfg {
  * (both pruning passes, with them the W2.T copy and, fp8, the weight quantisation) and reads what that call left.  Every output is the
  * same bits as without the flag.  The library cannot check the promise.  fp8: amax[1], amax[2] (w1, w2) come back as 0. */
 #define SFFN_FLAG_WEIGHTS_PACKED 16
+/* Same entry points (and their backward halves): dW1 and dW2 are float32 matrices of the same shapes ([F, D] and [D, F]; grouped:
+ * [n_experts, ...]) that the call ADDS to - dW32 = dW32 + (eq. (8) / eq. (5) in float32) - instead of bf16 matrices that it overwrites:
+ * the gradient buffers a training loop keeps across the micro-batches of an optimizer step (the amortisation of Section 3.4 presumes
+ * such micro-batches).  The pointers are passed through the uint16_t* parameters; the caller owns and zeroes the buffers.  Every
+ * element is updated by exactly one thread, so the sum is deterministic.  16-byte alignment as before. */
+#define SFFN_FLAG_DW_FP32_ACCUMULATE 32
 
 /* Byte offsets, inside the workspace of ffn_sparse_step, of the tensors Alg. 2 line 1 saves
  * from the forward pass and of the other intermediates (all filled when the step returns). */

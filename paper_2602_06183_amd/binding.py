@@ -208,6 +208,7 @@ FLAG_UNFUSED = 2
 FLAG_FP8_WGRAD = 4
 FLAG_LEAN = 8
 FLAG_WEIGHTS_PACKED = 16
+FLAG_DW_FP32_ACCUMULATE = 32
 
 
 def dense_sqrelu(y1, out):
@@ -227,6 +228,11 @@ def dense_dsqrelu(dy2, y1, out):
 
 def _cfg(T, D, F, mode=MODE_HARD, V=64, M=8, flags=0):
     return _Cfg(T, D, F, V, M, mode, flags)
+
+
+def _dw(shape, device, fp32):
+    """A weight-gradient output: bf16, overwritten by every call, or a float32 accumulator (zero) that every call adds to."""
+    return torch.zeros(shape, dtype=torch.float32, device=device) if fp32 else _bf16(shape, device)
 
 
 class _StepBuffers:
@@ -437,7 +443,8 @@ def vnm_wgrad(a_vals, a_meta, a_colidx, G, out_f_major, V=64, M=8):
 class FfnStep(_StepBuffers):
     """Pre-allocated outputs and workspace for repeated ffn_sparse_step calls on one shape."""
 
-    def __init__(self, T, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8, unfused=False, lean=False, scratch=None, weights_of=None):
+    def __init__(self, T, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8, unfused=False, lean=False, scratch=None, weights_of=None,
+                 dw_fp32=False):
         """keep_dense: also store the dense y1 and dy2 (SFFN_FLAG_KEEP_DENSE); otherwise only y1 at y2's kept
         slots is saved for the backward pass.  M: V:N:M block width, 8, 16, 32 or 64.  unfused (M >= 16): the path
         with separate eq. (2) / eq. (6) kernels that always stores y1 and dy2 and produces no y1_kept.  lean:
@@ -446,12 +453,13 @@ class FfnStep(_StepBuffers):
         calls are ordered on one stream can share it, each keeping only its saved and weights regions.  weights_of: another FfnStep of the same
         configuration whose weights region this object shares (a second micro-batch of one layer)."""
         self.T, self.D, self.F, self.mode, self.keep_dense, self.M = T, D, F, mode, keep_dense, M
-        self.cfg = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused, lean))
+        self.cfg = _cfg(T, D, F, mode, M=M, flags=_flags(keep_dense, unfused, lean) | (FLAG_DW_FP32_ACCUMULATE if dw_fp32 else 0))
         self.layout = workspace_layout(T, D, F, mode, M, keep_dense, unfused, lean)
         self.lean = lean and self.layout["w1_meta"] == self.layout["w1_vals"]       # (the unfused path ignores the flag)
         assert self._alloc_regions(load().sffn_buffer_sizes, 1, device, scratch, weights_of) == self.layout["total"]
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
-        self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
+        # dw_fp32 (SFFN_FLAG_DW_FP32_ACCUMULATE): dW1 / dW2 are float32 buffers, zero here, that every call adds its weight gradients to
+        self.dW1, self.dW2 = _dw((F, D), device, dw_fp32), _dw((D, F), device, dw_fp32)
 
     def __call__(self, X, W1, W2, b1, dY, weights_packed=False):
         T, D, F = self.T, self.D, self.F
@@ -511,18 +519,18 @@ class FfnStepGrouped(_StepBuffers):
     """Pre-allocated outputs and workspace for ffn_sparse_step_grouped: n_experts FFNs, expert e on token rows
     seg[e]..seg[e+1] (host integers, multiples of 64; T = seg[-1])."""
 
-    def __init__(self, seg, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8, lean=False, scratch=None):
+    def __init__(self, seg, D, F, mode=MODE_HARD, device="cuda", keep_dense=False, M=8, lean=False, scratch=None, dw_fp32=False):
         self.seg = [int(v) for v in seg]
         self.E, self.T, self.D, self.F, self.mode, self.keep_dense, self.M = len(self.seg) - 1, self.seg[-1], D, F, mode, keep_dense, M
         self.seg_c = (ctypes.c_int64 * len(self.seg))(*self.seg)
-        self.cfg = _cfg(self.T, D, F, mode, M=M, flags=_flags(keep_dense, False, lean))
+        self.cfg = _cfg(self.T, D, F, mode, M=M, flags=_flags(keep_dense, False, lean) | (FLAG_DW_FP32_ACCUMULATE if dw_fp32 else 0))
         lay = _Layout()
         _check(load().sffn_grouped_workspace_layout(ctypes.byref(self.cfg), self.E, ctypes.byref(lay)))
         self.layout = {n: getattr(lay, n) for n, _ in _Layout._fields_}
         self.lean = lean and self.layout["w1_meta"] == self.layout["w1_vals"]
         assert self._alloc_regions(load().sffn_buffer_sizes, self.E, device, scratch) == self.layout["total"]
         self.Y3, self.dX = _bf16((self.T, D), device), _bf16((self.T, D), device)
-        self.dW1, self.dW2 = _bf16((self.E, F, D), device), _bf16((self.E, D, F), device)
+        self.dW1, self.dW2 = _dw((self.E, F, D), device, dw_fp32), _dw((self.E, D, F), device, dw_fp32)
 
     def __call__(self, X, W1, W2, b1, dY, weights_packed=False):
         T, D, F, E = self.T, self.D, self.F, self.E
@@ -656,11 +664,11 @@ class FfnStepFp8(_StepBuffers):
     """ffn_sparse_step_fp8 with outputs and workspace allocated once.  scales: dict with the six per-tensor scales
     x, w1, w2, y2, dy, dy1 (positive floats; delayed scaling: the caller derives them from earlier steps)."""
 
-    def __init__(self, T, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False, M=8, scratch=None):
+    def __init__(self, T, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False, M=8, scratch=None, dw_fp32=False):
         """wgrad_fp8: eqs. (5), (8) contract codes as well (SFFN_FLAG_FP8_WGRAD); otherwise they are the bf16 contractions.
         lean: the canonical copies of the packed tensors are not written (SFFN_FLAG_LEAN).  M: columns per V:N:M block (8, 16, 32, 64)."""
         self.T, self.D, self.F, self.mode, self.M = T, D, F, mode, M
-        self.cfg = _cfg(T, D, F, mode, M=M, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0) | (FLAG_LEAN if lean else 0))
+        self.cfg = _cfg(T, D, F, mode, M=M, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0) | (FLAG_LEAN if lean else 0) | (FLAG_DW_FP32_ACCUMULATE if dw_fp32 else 0))
         self.scales = _Fp8Scales(*[float(scales[k]) for k in ("x", "w1", "w2", "y2", "dy", "dy1")])
         lay = _Fp8Layout()
         _check(load().sffn_fp8_workspace_layout(ctypes.byref(self.cfg), ctypes.byref(lay)))
@@ -669,7 +677,7 @@ class FfnStepFp8(_StepBuffers):
         self.lean = lean
         assert self._alloc_regions(load().sffn_fp8_buffer_sizes, 1, device, scratch) == self.layout["total"]
         self.Y3, self.dX = _bf16((T, D), device), _bf16((T, D), device)
-        self.dW1, self.dW2 = _bf16((F, D), device), _bf16((D, F), device)
+        self.dW1, self.dW2 = _dw((F, D), device, dw_fp32), _dw((D, F), device, dw_fp32)
         self.amax = torch.zeros((8,), dtype=torch.float32, device=device)        # [0:6]: x, w1, w2, y2, dy, dy1 after every call
 
     def set_scales(self, scales):
@@ -739,11 +747,11 @@ class FfnStepFp8(_StepBuffers):
 class FfnStepFp8Grouped(FfnStepFp8):
     """ffn_sparse_step_fp8_grouped: n_experts FFNs, expert e on token rows seg[e]..seg[e+1] (host integers, multiples of 64; T = seg[-1])."""
 
-    def __init__(self, seg, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False, M=8, scratch=None):
+    def __init__(self, seg, D, F, scales, mode=MODE_HARD, device="cuda", keep_dense=False, wgrad_fp8=False, lean=False, M=8, scratch=None, dw_fp32=False):
         self.seg = [int(v) for v in seg]
         self.E, self.T, self.D, self.F, self.mode, self.keep_dense, self.M = len(self.seg) - 1, self.seg[-1], D, F, mode, keep_dense, M
         self.seg_c = (ctypes.c_int64 * len(self.seg))(*self.seg)
-        self.cfg = _cfg(self.T, D, F, mode, M=M, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0) | (FLAG_LEAN if lean else 0))
+        self.cfg = _cfg(self.T, D, F, mode, M=M, flags=(FLAG_KEEP_DENSE if keep_dense else 0) | (FLAG_FP8_WGRAD if wgrad_fp8 else 0) | (FLAG_LEAN if lean else 0) | (FLAG_DW_FP32_ACCUMULATE if dw_fp32 else 0))
         self.set_scales(scales)
         lay = _Fp8Layout()
         _check(load().sffn_fp8_grouped_workspace_layout(ctypes.byref(self.cfg), self.E, ctypes.byref(lay)))
@@ -751,7 +759,7 @@ class FfnStepFp8Grouped(FfnStepFp8):
         self.lean = lean
         assert self._alloc_regions(load().sffn_fp8_buffer_sizes, self.E, device, scratch) == self.layout["total"]
         self.Y3, self.dX = _bf16((self.T, D), device), _bf16((self.T, D), device)
-        self.dW1, self.dW2 = _bf16((self.E, F, D), device), _bf16((self.E, D, F), device)
+        self.dW1, self.dW2 = _dw((self.E, F, D), device, dw_fp32), _dw((self.E, D, F), device, dw_fp32)
         self.amax = torch.zeros((8,), dtype=torch.float32, device=device)
 
     def __call__(self, X, W1, W2, b1, dY, weights_packed=False):

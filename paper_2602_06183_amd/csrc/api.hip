@@ -461,7 +461,7 @@ struct Fp8Layout {
 bool make_fp8_layout(const sffn_cfg* c, Fp8Layout* L, int n_experts = 1) {
     if (!c || !mult64(c->T) || !mult128(c->D) || !mult128(c->F) || c->V != 64 || n_experts < 1) return false;
     if (c->M != 8 && !(vnm_ok(c->V, c->M) && vnm_spmm_gather_fp8_ok(c->T, c->D, c->F, c->M))) return false;
-    if (c->flags & ~(SFFN_FLAG_KEEP_DENSE | SFFN_FLAG_FP8_WGRAD | SFFN_FLAG_LEAN | SFFN_FLAG_WEIGHTS_PACKED)) return false;
+    if (c->flags & ~(SFFN_FLAG_KEEP_DENSE | SFFN_FLAG_FP8_WGRAD | SFFN_FLAG_LEAN | SFFN_FLAG_WEIGHTS_PACKED | SFFN_FLAG_DW_FP32_ACCUMULATE)) return false;
     const bool dense = (c->flags & SFFN_FLAG_KEEP_DENSE) != 0;
     const bool lean = (c->flags & SFFN_FLAG_LEAN) != 0;              // canonical copies that are not written take no room
     const size_t T = c->T, D = c->D, F = (size_t)c->F * n_experts, TF = T * (size_t)c->F, M = (size_t)c->M;
@@ -507,7 +507,7 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "ffn_sparse_step_fp8: only V = 64 with M in {8, 16, 32, 64} is built");
     REQUIRE(make_fp8_layout(cfg, &L, n_experts), SFFN_EINVAL,
             "ffn_sparse_step_fp8: T must be a positive multiple of 64, D and F of 128 (M >= 16: 4 F / M a multiple of 128); flags: "
-            "SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD, SFFN_FLAG_LEAN, SFFN_FLAG_WEIGHTS_PACKED");
+            "SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD, SFFN_FLAG_LEAN, SFFN_FLAG_WEIGHTS_PACKED, SFFN_FLAG_DW_FP32_ACCUMULATE");
     REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_sparse_step_fp8: unknown mode");
     REQUIRE((!fwd || (X && W1 && W2 && Y3)) && (!bwd || (dY && dX && dW1 && dW2)), SFFN_EINVAL, "ffn_sparse_step_fp8: null pointer");
     REQUIRE(aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(dY) && aligned16(Y3) && aligned16(dX) && aligned16(dW1) && aligned16(dW2) &&
@@ -540,6 +540,7 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     uint16_t *xtb = (uint16_t*)(rg.at(L.xt_blk)), *dytb = (uint16_t*)(rg.at(L.dyt_blk)), *atb = (uint16_t*)(rg.at(L.at_blk));
     uint8_t *v24 = rg.at(L.v24), *m24 = rg.at(L.m24), *kmask = rg.at(L.kmask);
     const int keep_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0;
+    const bool acc32 = (cfg->flags & SFFN_FLAG_DW_FP32_ACCUMULATE) != 0;      // dW1 / dW2 are float32 accumulators that eqs. (8) / (5) add to
     const bool w8 = (cfg->flags & SFFN_FLAG_FP8_WGRAD) != 0;      // eqs. (5), (8) on codes too: X.T, dY.T and the compact transposed survivors as codes
     if (cfg->flags & SFFN_FLAG_LEAN) {      // no canonical copies of the packed tensors (dy1 stays: eq. (8) in bf16 does not need it either, but it is small)
         w1c = w1m = w2c = w2m = nullptr;
@@ -608,8 +609,8 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
         STAGE(launch_quantize_fp8_blocked(dY, T, D, D, idy, dyq, s, ady), "step/quantize(dY)");
     }
     if (bwd) {
-        if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)dytb, sc->y2 * sc->dy, F, D, T, 1, dW2, F, s, gw), "step/dW2");   // eq. (5) on codes
-        else STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");               // eq. (5), bf16
+        if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)dytb, sc->y2 * sc->dy, F, D, T, 1, dW2, F, s, gw, acc32), "step/dW2");   // eq. (5) on codes
+        else STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw, acc32), "step/dW2");               // eq. (5), bf16
     }
     if (bwd) {   // eq. (4) on codes, then eq. (6) in bf16 on y2's kept slots; dy1 leaves as codes (eq. (7)) and, at M = 8, in bf16 (canonical)
         VnmEpilogue ep;
@@ -623,8 +624,8 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
         else STAGE(launch_vnm8_gemm_fp8(vcb, mcb, cixt, w1q, D, sc->dy1 * sc->w1, T, D, F, dX, D, s, gr), "step/dX");
     }
     if (bwd) {
-        if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)xtb, sc->dy1 * sc->x, F, D, T, 0, dW1, D, s, gw), "step/dW1");   // eq. (8) on codes
-        else STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                // eq. (8), bf16
+        if (w8) STAGE(launch_wgrad_vnm_fp8((const uint8_t*)atb, kmask, (const uint8_t*)xtb, sc->dy1 * sc->x, F, D, T, 0, dW1, D, s, gw, acc32), "step/dW1");   // eq. (8) on codes
+        else STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw, acc32), "step/dW1");                // eq. (8), bf16
     }
     if (amax) STAGE(launch_amax_finish(slot_of(a_first), a_count, amax + a_first, s), "step/finish(amax)");
     return SFFN_OK;
@@ -834,7 +835,8 @@ static int run_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, cons
     RouterLayout L;
     REQUIRE(make_router_layout(cfg, &L), SFFN_EINVAL, "ffn_router_step: T > 0, D and F positive multiples of 64, 4F/M a multiple of 64");
     REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_router_step: unknown mode");
-    REQUIRE(!(cfg->flags & SFFN_FLAG_WEIGHTS_PACKED), SFFN_EUNSUPPORTED, "ffn_router_step: SFFN_FLAG_WEIGHTS_PACKED is not built for the router's step");
+    REQUIRE(!(cfg->flags & (SFFN_FLAG_WEIGHTS_PACKED | SFFN_FLAG_DW_FP32_ACCUMULATE)), SFFN_EUNSUPPORTED,
+            "ffn_router_step: SFFN_FLAG_WEIGHTS_PACKED and SFFN_FLAG_DW_FP32_ACCUMULATE are not built for the router's step");
     const int64_t T = cfg->T, D = cfg->D, F = cfg->F;
     const int M = cfg->M, E = M / 4;
     const int64_t Kc = 4 * F / M, rows = sffn_venom_rows(T, M);
@@ -1021,7 +1023,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     REQUIRE(cfg->M == 8 || fused_wide(cfg) || (seg == nullptr && n_experts == 1), SFFN_EUNSUPPORTED,
             "ffn_sparse_step_grouped: blocks of 16 / 32 / 64 columns need 4 F / M to be a multiple of 64 and at most 7168 (and no SFFN_FLAG_UNFUSED)");
     REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_sparse_step: unknown mode");
-    REQUIRE(!(cfg->flags & ~(SFFN_FLAG_KEEP_DENSE | SFFN_FLAG_UNFUSED | SFFN_FLAG_FP8_WGRAD | SFFN_FLAG_LEAN | SFFN_FLAG_WEIGHTS_PACKED)), SFFN_EINVAL,
+    REQUIRE(!(cfg->flags & ~(SFFN_FLAG_KEEP_DENSE | SFFN_FLAG_UNFUSED | SFFN_FLAG_FP8_WGRAD | SFFN_FLAG_LEAN | SFFN_FLAG_WEIGHTS_PACKED | SFFN_FLAG_DW_FP32_ACCUMULATE)), SFFN_EINVAL,
             "ffn_sparse_step: unknown flag");
     REQUIRE(aligned16(X) && aligned16(W1) && aligned16(W2) && aligned16(b1) && aligned16(dY) && aligned16(Y3) && aligned16(dX) &&
                 aligned16(dW1) && aligned16(dW2) && aligned16(workspace),
@@ -1067,6 +1069,9 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     // the conversion is paid once per optimizer step, not once per micro-batch)
     const bool packed = (cfg->flags & SFFN_FLAG_WEIGHTS_PACKED) != 0;
     REQUIRE(!packed || cfg->M == 8 || fused_wide(cfg), SFFN_EUNSUPPORTED, "ffn_sparse_step: SFFN_FLAG_WEIGHTS_PACKED is not built for the unfused path");
+    // SFFN_FLAG_DW_FP32_ACCUMULATE: dW1 / dW2 are float32 accumulators that eqs. (8) / (5) add to (micro-batches of one optimizer step)
+    const bool acc32 = (cfg->flags & SFFN_FLAG_DW_FP32_ACCUMULATE) != 0;
+    REQUIRE(!acc32 || cfg->M == 8 || fused_wide(cfg), SFFN_EUNSUPPORTED, "ffn_sparse_step: SFFN_FLAG_DW_FP32_ACCUMULATE is not built for the unfused path");
     REQUIRE(phase == 3 || cfg->M == 8 || fused_wide(cfg), SFFN_EUNSUPPORTED, "ffn_sparse_forward / ffn_sparse_backward: not built for the unfused path");
     if (fused_wide(cfg)) {
         // Blocks of M = 16, 32, 64 columns (Table 5), fused like the M = 8 step: eq. (2) + compression in the epilogue of eq. (1), eq. (6)
@@ -1094,14 +1099,14 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
         if (fwd && !packed) STAGE(launch_prune24_step(W2, F, D, F, 1, cfg->mode, lean_w ? nullptr : w2v, lean_w ? nullptr : w2m, w2vb, w2mb, nullptr, s, (int)E, 0, w2t), "step/prune24(W2.T)");
         if (fwd) STAGE(launch_vnm_spmm_gather(y2v, y2m, cix, w2t, D, T, D, F, M, Y3, D, s, gr), "step/y3");                              // eq. (3)
         if (bwd) STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
-        if (bwd) STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");                                       // eq. (5)
+        if (bwd) STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw, acc32), "step/dW2");                                       // eq. (5)
         if (bwd) {
             VnmEpilogue ep;
             ep.mode = 6; ep.logM = logM; ep.store_dense = keep_dense; ep.vals = dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept; ep.at = atb;
             STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, ep, s, gp), "step/dy2+dsqrelu_vnm");         // eqs. (4), (6)
         }
         if (bwd) STAGE(launch_vnm_spmm_gather(dy1v, y2m, cix, W1, D, T, D, F, M, dX, D, s, gr), "step/dX");                              // eq. (7), dense W1 as is
-        if (bwd) STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                                        // eq. (8)
+        if (bwd) STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw, acc32), "step/dW1");                                        // eq. (8)
         return SFFN_OK;
     }
     if (cfg->M != 8) {
@@ -1186,7 +1191,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     if (fwd) STAGE(launch_vnm8_gemm(vcb, mcb, cixt, w2t, D, T, D, F, Y3, D, s, gd), "step/y3");                         // eq. (3)
     // ---- Alg. 2 -------------------------------------------------------------------------------
     if (bwd) STAGE(launch_transpose(dY, T, D, D, dytb, 1, dyb, s), "step/dY.T");
-    if (bwd) STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw), "step/dW2");                          // eq. (5)
+    if (bwd) STAGE(launch_wgrad_vnm(atb, kmask, dytb, F, D, T, 1, dW2, F, s, gw, acc32), "step/dW2");                          // eq. (5)
     if (bwd) {   // eq. (4), then eq. (6) on y2's kept slots; overwrites the survivors and the transposed tile with dy1's
         VnmEpilogue ep;
         ep.mode = 2; ep.store_dense = keep_dense; ep.vals = lean ? nullptr : dy1v; ep.meta = y2m; ep.colidx = cix; ep.ykept = ykept;
@@ -1194,7 +1199,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
         STAGE(launch_gemm_vnm_epilogue(w2vb, w2mb, dyb, nullptr, F, T, D, dy2, ep, s, gp), "step/dy2+dsqrelu_vnm");
     }
     if (bwd) STAGE(launch_vnm8_gemm(vcb, mcb, cixt, W1, D, T, D, F, dX, D, s, gd), "step/dX");                          // eq. (7), dense W1 as is
-    if (bwd) STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw), "step/dW1");                           // eq. (8)
+    if (bwd) STAGE(launch_wgrad_vnm(atb, kmask, xtb, F, D, T, 0, dW1, D, s, gw, acc32), "step/dW1");                           // eq. (8)
     (void)w1tb;
     return SFFN_OK;
 }

@@ -29,12 +29,87 @@ constexpr int kLoads = 2 + 4 + 1;                // LDS-DMA loads per wavefront 
 }  // namespace
 
 // Accumulators of one 128 x 64 wave tile -> bf16 output (one rounding; `alpha` = product of the operand scales of the fp8 form, 1 otherwise).
-template <bool OUT_I_CONTIG>
+// ACC32: `out` is a float32 matrix of the same shape that the tile is ADDED to (gradient accumulation over the micro-batches of an
+// optimizer step): out32 = out32 + alpha * sum, both in float32.
+template <bool OUT_I_CONTIG, bool ACC32>
 __device__ __forceinline__ void wgrad_store(f32x16 (&acc)[4][2], float alpha, unsigned char* smem, int wave, int lane, int i0, int j0, int F, int N,
                                             uint16_t* __restrict__ out, int64_t ldo) {
     constexpr int WM = 128, WN = 64, FM = 4, FN = 2;
     const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, lh = lane >> 5;
-    if (OUT_I_CONTIG) {
+    if (ACC32 && OUT_I_CONTIG) {
+        // out32[j * ldo + i]: a lane owns 4 consecutive i of one j; stage [32 j][64 i] through LDS so that HBM sees 256-byte row
+        // segments in 16-byte accesses (read, add, write)
+        float* out32 = reinterpret_cast<float*>(out);
+        constexpr int EP = 64 * 4 + 16;
+        unsigned char* scratch = smem + wave * (32 * EP);
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int b = 0; b < FN; ++b) {
+                const int f0 = i0 + wm * WM + h * 64, n0 = j0 + wn * WN + b * 32;
+#pragma unroll
+                for (int a2 = 0; a2 < 2; ++a2)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int a = 2 * h + a2;
+                        *reinterpret_cast<float4*>(scratch + l32 * EP + (a2 * 32 + 8 * g + 4 * lh) * 4) =
+                            make_float4(acc[a][b][4 * g] * alpha, acc[a][b][4 * g + 1] * alpha, acc[a][b][4 * g + 2] * alpha, acc[a][b][4 * g + 3] * alpha);
+                    }
+                wave_lds_sync();
+                // all of the slab's old values are requested before the first sum is stored (a store would otherwise stand between the loads)
+                float4 old[8];
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    const int row = p * 4 + (lane >> 4), ch = lane & 15;
+                    const int j = n0 + row, i = f0 + ch * 4;
+                    old[p] = (j < N && i < F) ? *reinterpret_cast<const float4*>(out32 + (int64_t)j * ldo + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    const int row = p * 4 + (lane >> 4), ch = lane & 15;
+                    const int j = n0 + row, i = f0 + ch * 4;
+                    if (j < N && i < F) {
+                        const float4 add = *reinterpret_cast<const float4*>(scratch + row * EP + ch * 16);
+                        *reinterpret_cast<float4*>(out32 + (int64_t)j * ldo + i) = make_float4(old[p].x + add.x, old[p].y + add.y, old[p].z + add.z, old[p].w + add.w);
+                    }
+                }
+                wave_lds_sync();
+            }
+    } else if (ACC32) {
+        // out32[i * ldo + j]: each 32-row slab goes through LDS, as in the bf16 form below, for 16-byte accesses on 256-byte row segments;
+        // the products are rounded to float32 before they are staged, so the addition is never a fused multiply-add
+        float* out32 = reinterpret_cast<float*>(out);
+        constexpr int EP = WN * 4 + 16;
+        unsigned char* scratch = smem + wave * (32 * EP);
+#pragma unroll
+        for (int a = 0; a < FM; ++a) {
+#pragma unroll
+            for (int b = 0; b < FN; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 8 * (r >> 2) + 4 * lh + (r & 3);
+                    *reinterpret_cast<float*>(scratch + row * EP + (b * 32 + l32) * 4) = acc[a][b][r] * alpha;
+                }
+            wave_lds_sync();
+            float4 old[8];
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int row = p * 4 + (lane >> 4), ch = lane & 15;
+                const int i = i0 + wm * WM + a * 32 + row, j = j0 + wn * WN + ch * 4;
+                old[p] = (i < F && j < N) ? *reinterpret_cast<const float4*>(out32 + (int64_t)i * ldo + j) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int row = p * 4 + (lane >> 4), ch = lane & 15;
+                const int i = i0 + wm * WM + a * 32 + row, j = j0 + wn * WN + ch * 4;
+                if (i < F && j < N) {
+                    const float4 add = *reinterpret_cast<const float4*>(scratch + row * EP + ch * 16);
+                    *reinterpret_cast<float4*>(out32 + (int64_t)i * ldo + j) = make_float4(old[p].x + add.x, old[p].y + add.y, old[p].z + add.z, old[p].w + add.w);
+                }
+            }
+            wave_lds_sync();
+        }
+    } else if (OUT_I_CONTIG) {
         // out[j * ldo + i]: a lane owns 4 consecutive i of one j; stage [j][i] through LDS (two halves of 64 i)
         // so that HBM sees 128-byte row segments
         constexpr int EP = 64 * 2 + 16;
@@ -88,7 +163,7 @@ __device__ __forceinline__ void wgrad_store(f32x16 (&acc)[4][2], float alpha, un
     }
 }
 
-template <bool OUT_I_CONTIG>
+template <bool OUT_I_CONTIG, bool ACC32>
 __global__ void __launch_bounds__(512) wgrad_vnm_kernel(const uint16_t* __restrict__ atc, const uint8_t* __restrict__ kmask,
                                                        const uint16_t* __restrict__ G, int F, int N, int Ttot,
                                                        uint16_t* __restrict__ out, int64_t ldo, int tiles_m, int tiles_n,
@@ -113,7 +188,7 @@ __global__ void __launch_bounds__(512) wgrad_vnm_kernel(const uint16_t* __restri
         L -= e * per;
         k_base = grp.seg[e];
         K = grp.seg[e + 1] - k_base;
-        out += e * grp.out_stride;
+        out += e * grp.out_stride * (ACC32 ? 2 : 1);          // (float32 elements are two uint16_t wide)
     }
     int tm, tn;
     {
@@ -290,7 +365,7 @@ __global__ void __launch_bounds__(512) wgrad_vnm_kernel(const uint16_t* __restri
 #undef SB
     __syncthreads();
 
-    wgrad_store<OUT_I_CONTIG>(acc, 1.0f, smem, wave, lane, i0, j0, F, N, out, ldo);
+    wgrad_store<OUT_I_CONTIG, ACC32>(acc, 1.0f, smem, wave, lane, i0, j0, F, N, out, ldo);
 }
 
 // The same contraction on E4M3 codes (the fp8 step with SFFN_FLAG_FP8_WGRAD): atc and G hold one code per element, in the blocked layout
@@ -307,7 +382,7 @@ constexpr int k8Stages = 5;
 constexpr int k8Loads = 1 + 1 + 2;               // mask, A block, two G blocks per wavefront and stage
 }  // namespace
 
-template <bool OUT_I_CONTIG>
+template <bool OUT_I_CONTIG, bool ACC32>
 __global__ void __launch_bounds__(512) wgrad_vnm_fp8_kernel(const uint16_t* __restrict__ atc, const uint8_t* __restrict__ kmask,
                                                            const uint16_t* __restrict__ G, int F, int N, int Ttot, float alpha,
                                                            uint16_t* __restrict__ out, int64_t ldo, int tiles_m, int tiles_n, GemmGroup grp) {
@@ -330,7 +405,7 @@ __global__ void __launch_bounds__(512) wgrad_vnm_fp8_kernel(const uint16_t* __re
         L -= e * per;
         k_base = grp.seg[e];
         K = grp.seg[e + 1] - k_base;
-        out += e * grp.out_stride;
+        out += e * grp.out_stride * (ACC32 ? 2 : 1);          // (float32 elements are two uint16_t wide)
     }
     int tm, tn;
     {
@@ -468,11 +543,11 @@ __global__ void __launch_bounds__(512) wgrad_vnm_fp8_kernel(const uint16_t* __re
     }
 #undef SB
     __syncthreads();
-    wgrad_store<OUT_I_CONTIG>(acc, alpha, smem, wave, lane, i0, j0, F, N, out, ldo);
+    wgrad_store<OUT_I_CONTIG, ACC32>(acc, alpha, smem, wave, lane, i0, j0, F, N, out, ldo);
 }
 
 hipError_t launch_wgrad_vnm_fp8(const uint8_t* atc, const uint8_t* kmask, const uint8_t* Gq, float alpha, int64_t F, int64_t N, int64_t T,
-                                int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp) {
+                                int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp, bool acc32) {
     if (T % 64 != 0 || T <= 0) return hipErrorInvalidValue;
     const int tiles_m = (int)((F + 255) / 256), tiles_n = (int)((N + 255) / 256);
     const GemmGroup gg = grp ? *grp : GemmGroup();
@@ -480,23 +555,31 @@ hipError_t launch_wgrad_vnm_fp8(const uint8_t* atc, const uint8_t* kmask, const 
     dim3 grid((unsigned)(tiles_m * tiles_n * (gg.n ? gg.n : 1)));
     const uint16_t* a = reinterpret_cast<const uint16_t*>(atc);
     const uint16_t* g = reinterpret_cast<const uint16_t*>(Gq);
-    if (out_i_contig)
-        hipLaunchKernelGGL((wgrad_vnm_fp8_kernel<true>), grid, dim3(512), 0, s, a, kmask, g, (int)F, (int)N, (int)T, alpha, out, ldo, tiles_m, tiles_n, gg);
+    if (out_i_contig && acc32)
+        hipLaunchKernelGGL((wgrad_vnm_fp8_kernel<true, true>), grid, dim3(512), 0, s, a, kmask, g, (int)F, (int)N, (int)T, alpha, out, ldo, tiles_m, tiles_n, gg);
+    else if (out_i_contig)
+        hipLaunchKernelGGL((wgrad_vnm_fp8_kernel<true, false>), grid, dim3(512), 0, s, a, kmask, g, (int)F, (int)N, (int)T, alpha, out, ldo, tiles_m, tiles_n, gg);
+    else if (acc32)
+        hipLaunchKernelGGL((wgrad_vnm_fp8_kernel<false, true>), grid, dim3(512), 0, s, a, kmask, g, (int)F, (int)N, (int)T, alpha, out, ldo, tiles_m, tiles_n, gg);
     else
-        hipLaunchKernelGGL((wgrad_vnm_fp8_kernel<false>), grid, dim3(512), 0, s, a, kmask, g, (int)F, (int)N, (int)T, alpha, out, ldo, tiles_m, tiles_n, gg);
+        hipLaunchKernelGGL((wgrad_vnm_fp8_kernel<false, false>), grid, dim3(512), 0, s, a, kmask, g, (int)F, (int)N, (int)T, alpha, out, ldo, tiles_m, tiles_n, gg);
     return hipGetLastError();
 }
 
 hipError_t launch_wgrad_vnm(const uint16_t* atc, const uint8_t* kmask, const uint16_t* G, int64_t F, int64_t N, int64_t T,
-                            int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp) {
+                            int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp, bool acc32) {
     const int tiles_m = (int)((F + 255) / 256), tiles_n = (int)((N + 255) / 256);
     const GemmGroup g = grp ? *grp : GemmGroup();
     if (g.n && (g.n > GemmGroup::kMaxExperts || g.role != 2)) return hipErrorInvalidValue;
     dim3 grid((unsigned)(tiles_m * tiles_n * (g.n ? g.n : 1)));
-    if (out_i_contig)
-        hipLaunchKernelGGL((wgrad_vnm_kernel<true>), grid, dim3(512), 0, s, atc, kmask, G, (int)F, (int)N, (int)T, out, ldo, tiles_m, tiles_n, g);
+    if (out_i_contig && acc32)
+        hipLaunchKernelGGL((wgrad_vnm_kernel<true, true>), grid, dim3(512), 0, s, atc, kmask, G, (int)F, (int)N, (int)T, out, ldo, tiles_m, tiles_n, g);
+    else if (out_i_contig)
+        hipLaunchKernelGGL((wgrad_vnm_kernel<true, false>), grid, dim3(512), 0, s, atc, kmask, G, (int)F, (int)N, (int)T, out, ldo, tiles_m, tiles_n, g);
+    else if (acc32)
+        hipLaunchKernelGGL((wgrad_vnm_kernel<false, true>), grid, dim3(512), 0, s, atc, kmask, G, (int)F, (int)N, (int)T, out, ldo, tiles_m, tiles_n, g);
     else
-        hipLaunchKernelGGL((wgrad_vnm_kernel<false>), grid, dim3(512), 0, s, atc, kmask, G, (int)F, (int)N, (int)T, out, ldo, tiles_m, tiles_n, g);
+        hipLaunchKernelGGL((wgrad_vnm_kernel<false, false>), grid, dim3(512), 0, s, atc, kmask, G, (int)F, (int)N, (int)T, out, ldo, tiles_m, tiles_n, g);
     return hipGetLastError();
 }
 

@@ -206,9 +206,11 @@ hipError_t launch_prune24_fp8_step(const uint16_t* src, int64_t R, int64_t K, in
 
 // the same on E4M3 codes (atc: compact transposed codes [F / 2, T], Gq [N, T], both in the blocked pair layout): out = bf16(alpha * sum)
 hipError_t launch_wgrad_vnm_fp8(const uint8_t* atc, const uint8_t* kmask, const uint8_t* Gq, float alpha, int64_t F, int64_t N, int64_t T,
-                                int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
+                                int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr, bool acc32 = false);
+// acc32: `out` is a float32 matrix of the same shape (ldo in float32 elements; grouped form: out_stride in float32 elements) that the
+// result is added to, out32 += alpha * sum, instead of a bf16 matrix that is overwritten
 hipError_t launch_wgrad_vnm(const uint16_t* atc, const uint8_t* kmask, const uint16_t* G, int64_t F, int64_t N, int64_t T,
-                            int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr);
+                            int out_i_contig, uint16_t* out, int64_t ldo, hipStream_t s, const GemmGroup* grp = nullptr, bool acc32 = false);
 
 
 }  // namespace sffn

@@ -96,6 +96,7 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     assert lib.ffn_sparse_backward(ctypes.byref(wide_unfused), fake, fake, fake, fake, fake, ctypes.byref(big), None) == -2   # unfused path
     assert lib.ffn_sparse_forward_grouped(ctypes.byref(cfg), 2, None, fake, fake, fake, fake, fake, ctypes.byref(big), None) == -1
     assert lib.ffn_sparse_backward_grouped(ctypes.byref(cfg), 2, None, fake, fake, fake, fake, fake, ctypes.byref(big), None) == -1
+    assert lib.ffn_sparse_step(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 16, 0, 2 | 32)), *args, fake, 1 << 40, None) == -2   # float32 accumulation: fused paths only
     # SFFN_FLAG_WEIGHTS_PACKED (16) exists for the fused paths only: the unfused wide-block path (flag 2) refuses it before any launch
     assert lib.ffn_sparse_step(ctypes.byref(binding._Cfg(512, 256, 1024, 64, 16, 0, 2 | 16)), *args, fake, 1 << 40, None) == -2
     # the fp8 step: scales are a host struct; shapes, flags, scales and the workspace are checked before anything is enqueued
@@ -177,6 +178,7 @@ def test_router_entry_points_validate_on_the_host():
     m12 = binding._Cfg(100, 64, 1024, 64, 12, 0, 0)
     assert lib.ffn_router_step(ctypes.byref(m12), ok, *args, fake, big, None) == -2
     assert lib.ffn_router_step(ctypes.byref(binding._Cfg(cfg.T, cfg.D, cfg.F, 64, cfg.M, 0, 16)), ok, *args, fake, big, None) == -2     # no packed-weights form
+    assert lib.ffn_router_step(ctypes.byref(binding._Cfg(cfg.T, cfg.D, cfg.F, 64, cfg.M, 0, 32)), ok, *args, fake, big, None) == -2     # no float32 accumulation
     assert lib.sffn_router_full_workspace_bytes(ctypes.byref(cfg)) > lib.sffn_router_workspace_bytes(ctypes.byref(cfg))
     assert lib.sffn_router_full_workspace_bytes(ctypes.byref(bad)) == 0
     assert lib.ffn_router_full_step(ctypes.byref(cfg), *args, fake, 16, None) == -3

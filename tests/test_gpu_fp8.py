@@ -435,6 +435,17 @@ def test_fp8_grouped_forward_and_backward_as_separate_calls_are_bit_identical():
     assert split.amax_dict() == whole.amax_dict()
 
 
+@pytest.mark.parametrize("M,wgrad_fp8", [(8, True), (8, False), (16, True)])
+def test_fp8_step_weight_gradients_accumulate_in_float32(M, wgrad_fp8):
+    from tests.test_gpu_kernels import _check_fp32_accumulation
+    T, D, F = 320, 256, 1024
+    inp = [make_ffn_inputs(T, D, F, seed=71 + i) for i in range(2)]
+    sc = dict(x=5.0 / 448, w1=0.1 / 448, w2=0.1 / 448, y2=8.0 / 448, dy=5.0 / 448, dy1=2.0 / 448)
+    W1, W2, b1 = to_dev(inp[0]["W1"]), to_dev(inp[0]["W2"]), to_dev(inp[0]["b1"])
+    batches = [(to_dev(i["X"]), W1, W2, b1, to_dev(i["dY"])) for i in inp]
+    _check_fp32_accumulation(lambda f32: sffn.FfnStepFp8(T, D, F, sc, sffn.MODE_HARD, wgrad_fp8=wgrad_fp8, M=M, dw_fp32=f32), batches)
+
+
 @pytest.mark.parametrize("wgrad_fp8", [False, True])
 def test_grouped_fp8_step_matches_oracle_per_expert(wgrad_fp8):
     """The mixture-of-experts form of the fp8 step (uneven segments, one of them empty): every expert's share is checked

@@ -851,6 +851,41 @@ def test_grouped_forward_and_backward_as_separate_calls_are_bit_identical():
         assert np.array_equal(x, y), name
 
 
+def _check_fp32_accumulation(make_step, batches):
+    """SFFN_FLAG_DW_FP32_ACCUMULATE: dW1 / dW2 are float32 buffers that every call adds to.  Exact statements: (1) from zero, one call leaves
+    the float32 value whose bf16 rounding is the plain step's dW, bit for bit (same accumulators, one rounding less); (2) a second call
+    leaves fl32(first + what that call leaves in a zero buffer); (3) Y3 and dX do not change."""
+    plain, acc, fresh = make_step(False), make_step(True), make_step(True)
+    assert acc.dW1.dtype == torch.float32 and not acc.dW1.any()
+    want = [to_bits(t).copy() for t in plain(*batches[0])]
+    got = acc(*batches[0])
+    assert np.array_equal(to_bits(got[0]), want[0]) and np.array_equal(to_bits(got[1]), want[1])
+    g1 = [acc.dW1.clone(), acc.dW2.clone()]
+    for g, w, name in zip(g1, want[2:], ("dW1", "dW2")):
+        assert g.abs().max() > 0 and np.array_equal(to_bits(g.to(torch.bfloat16)), w), name
+    acc(*batches[1])
+    fresh(*batches[1])
+    assert torch.equal(acc.dW1, g1[0] + fresh.dW1) and torch.equal(acc.dW2, g1[1] + fresh.dW2)
+
+
+@pytest.mark.parametrize("M", [8, 32])
+def test_weight_gradients_accumulate_in_float32(M):
+    T, D, F = 320, 256, 1024
+    inp = [make_ffn_inputs(T, D, F, seed=61 + i) for i in range(2)]
+    W1, W2, b1 = to_dev(inp[0]["W1"]), to_dev(inp[0]["W2"]), to_dev(inp[0]["b1"])
+    batches = [(to_dev(i["X"]), W1, W2, b1, to_dev(i["dY"])) for i in inp]
+    _check_fp32_accumulation(lambda f32: sffn.FfnStep(T, D, F, sffn.MODE_SOFT, M=M, dw_fp32=f32), batches)
+
+
+def test_grouped_weight_gradients_accumulate_in_float32():
+    D, F = 192, 320
+    m = make_moe_inputs(n_tokens=900, n_experts=4, top_k=2, D=D, F=F, seed=7)
+    dev = {k: to_dev(m[k]) for k in ("X", "W1", "W2", "b1", "dY")}
+    batches = [(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"]),
+               (torch.flip(dev["X"], (1,)).contiguous(), dev["W1"], dev["W2"], dev["b1"], torch.flip(dev["dY"], (1,)).contiguous())]
+    _check_fp32_accumulation(lambda f32: sffn.FfnStepGrouped(m["seg"], D, F, dw_fp32=f32), batches)
+
+
 def test_lean_grouped_step_is_bit_identical():
     D, F = 192, 320
     m = make_moe_inputs(n_tokens=900, n_experts=4, top_k=2, D=D, F=F, seed=2)
