@@ -73,8 +73,8 @@ typedef struct sffn_cfg {
 /* ffn_sparse_step / ffn_sparse_step_grouped: do not write the canonical copies w1_vals / w1_meta, w2t_vals / w2t_meta and, at M = 8,
  * y2_vals and dy1_vals of sffn_ws_layout (at M >= 16 eqs. (3), (7) read those two).  They are inspection aids: every consumer inside the
  * step reads its own operand layouts, and Y3, dX, dW1, dW2, y2_meta, colidx, y1_kept are the same bits with or without the flag.  Ignored
- * by the unfused path. */
-/* (With the flag those regions of the workspace are empty, 0 bytes: sffn_workspace_bytes() and the layouts depend on it.) */
+ * by the unfused path.  With the flag those regions of the workspace are empty (0 bytes): sffn_workspace_bytes() and the layouts
+ * depend on it.  The fp8 steps have the same flag (w1 / w2t codes and metadata; at M = 8 y2_codes). */
 #define SFFN_FLAG_LEAN 8
 /* ffn_sparse_step, ffn_sparse_step_grouped, ffn_sparse_step_fp8, ffn_sparse_step_fp8_grouped (not the unfused path, not the router
  * steps: SFFN_EUNSUPPORTED there): the weights are already packed.  Section 3.4 notes that the conversion of a weight to 2:4 is paid
@@ -92,12 +92,14 @@ typedef struct sffn_cfg {
 #define SFFN_FLAG_DW_FP32_ACCUMULATE 32
 
 /* Byte offsets, inside the workspace of ffn_sparse_step, of the tensors Alg. 2 line 1 saves
- * from the forward pass and of the other intermediates (all filled when the step returns). */
+ * from the forward pass and of the other intermediates (all filled when the step returns).  The workspace is three regions laid
+ * end to end, [scratch | saved | weights] (see sffn_buffers below): y1, dy2, y2_vals, dy1_vals lie in the first, y2_meta, colidx,
+ * y1_kept in the second, the packed weights in the third. */
 typedef struct sffn_ws_layout {
     size_t w1_vals, w1_meta;        /* sparsify24(W1):   [F, D/2] bf16, [F, D/8] u8 */
     size_t w2t_vals, w2t_meta;      /* sparsify24(W2.T): [F, D/2] bf16, [F, D/8] u8 */
-    size_t y1;                      /* [T, F] bf16, eq. (1) plus bias.  Present with SFFN_FLAG_KEEP_DENSE or M > 8; otherwise the
-                                     * region is empty (0 bytes) and the workspace is smaller by 2 * 2 T F bytes (y1 and dy2) */
+    size_t y1;                      /* [T, F] bf16, eq. (1) plus bias.  Present with SFFN_FLAG_KEEP_DENSE and on the unfused path; otherwise
+                                     * the region is empty (0 bytes) and the workspace is smaller by 2 * 2 T F bytes (y1 and dy2) */
     size_t y2_vals, y2_meta, colidx;/* V:N:M y2: [T, F/4] bf16, [T, F/16] u8, [T/64, F/8, 4] u8 */
     size_t dy2;                     /* [T, F] bf16, eq. (4); present under the same condition as y1 */
     size_t dy1_vals;                /* [T, F/4] bf16, eq. (6) in y2's slots */
