@@ -226,7 +226,7 @@ int vnm_spmm_fp8(const uint8_t* a_codes, const uint8_t* a_meta, const uint8_t* a
  * Shapes: V = 64, M in {8, 16, 32, 64} (Table 5's blocks), T a multiple of 64, D and F multiples of 128, for M >= 16 also 4 F / M a
  * multiple of 128 (eqs. (3), (7) then contract only the kept rows of the quantised W2.T / W1, gathered per token block);
  * cfg->flags: any of SFFN_FLAG_KEEP_DENSE, SFFN_FLAG_FP8_WGRAD, SFFN_FLAG_LEAN (the canonical w1 / w2t codes + meta and, at M = 8, the
- * y2 codes are not written).
+ * y2 codes are not written and take no room), SFFN_FLAG_WEIGHTS_PACKED, SFFN_FLAG_DW_FP32_ACCUMULATE.
  * Workspace: sffn_fp8_workspace_bytes(cfg); after the call it holds, at the offsets of sffn_fp8_workspace_layout: the pruned
  * weights (codes [F, D/2] u8 + meta [F, D/8]), y2 (codes [T, 2F/M] u8, meta [T, F/(2M)], colidx [T/64, F/M, 4]), dy1 at y2's slots
  * (dy1_vals: bf16 [T, F/4] at M = 8, codes [T, 2F/M] u8 at M >= 16), y1 at y2's slots (y1_kept, laid out as in ffn_sparse_step) and,
