@@ -127,7 +127,7 @@ bool make_layout(const sffn_cfg* c, FullLayout* L, int n_experts = 1) {
 
 extern "C" {
 
-int sffn_version(void) { return 101; }
+int sffn_version(void) { return 110; }
 const char* sffn_last_error(void) { return g_err; }
 // internal (not declared in the public header): lets the library's other source files leave a text behind sffn_last_error()
 int sffn_noalloc_set_error(int code, const char* text) { return fail(code, "%s", text); }
