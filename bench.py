@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--headline-only", action="store_true", help="skip the other configurations, the stand-alone kernels and the micro-benchmarks (profiling runs)")
     ap.add_argument("--fp8", action="store_true", help="with --headline-only: also run the fp8 step (both weight-gradient variants) at the headline shape (profiling runs)")
+    ap.add_argument("--micro-batches", action="store_true",
+                    help="with --headline-only: also run the micro-batch variants (packed weights, separate forward / backward calls, float32 gradient accumulation; profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference kernel for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -303,6 +305,45 @@ def main():
                 fp8_step["wide_blocks_fp8_weight_gradients"] = wide8
         return fp8_step
 
+    def micro_section(hw, esteps, ewarm, sp_h, de_h):
+        # Section 3.4: a weight is converted to 2:4 once per optimizer step and the cost is amortised over the micro-batches that pass through
+        # the layer in between (pipeline parallelism / gradient accumulation).  SFFN_FLAG_WEIGHTS_PACKED = a micro-batch after the first: both
+        # pruning passes skipped, same outputs.  Reported beside the headline, which always includes the pruning passes.
+        if hw.router:
+            return None
+        run_packed = lambda: hw.step(hw.X, hw.W1, hw.W2, hw.b1, hw.dY, weights_packed=True)
+        hw.sparse_step()
+        for _ in range(ewarm):
+            run_packed()
+        ms_p = timed(run_packed, esteps)
+        split_ms = None
+        if not hw.moe:      # Alg. 1 and Alg. 2 as separate calls (ffn_sparse_forward / ffn_sparse_backward): the step's launches in two halves
+            run_f = lambda: hw.step.forward(hw.X, hw.W1, hw.W2, hw.b1)
+            run_b = lambda: hw.step.backward(hw.W1, hw.dY)
+            run_f(); run_b()
+            split_ms = {"forward_ms": round(timed(run_f, esteps), 4), "backward_ms": round(timed(run_b, esteps), 4)}
+        accum = None
+        if not hw.moe:      # weight gradients summed over the micro-batches in float32: inside the weight-gradient GEMMs' epilogues
+                            # (SFFN_FLAG_DW_FP32_ACCUMULATE) against bf16 outputs + one add pass per weight in the framework
+            acc_step = sffn.FfnStep(hw.T, hw.D, hw.F, mode, M=hw.M, lean=True, dw_fp32=True)
+            main1, main2 = torch.zeros_like(acc_step.dW1), torch.zeros_like(acc_step.dW2)
+            run_fused = lambda: acc_step(hw.X, hw.W1, hw.W2, hw.b1, hw.dY, weights_packed=True)
+
+            def run_separate():
+                _, _, g1, g2 = hw.step(hw.X, hw.W1, hw.W2, hw.b1, hw.dY, weights_packed=True)
+                main1.add_(g1)
+                main2.add_(g2)
+            acc_step(hw.X, hw.W1, hw.W2, hw.b1, hw.dY)
+            run_fused(); run_separate()
+            accum = {"fused_into_the_weight_gradient_gemms_ms": round(timed(run_fused, esteps), 4),
+                     "bf16_outputs_plus_add_passes_ms": round(timed(run_separate, esteps), 4)}
+            del acc_step, main1, main2
+            free()
+        return {"weights_packed_ms_per_micro_batch": round(ms_p, 4), "speedup_vs_dense": round(de_h / ms_p, 4), "separate_calls": split_ms,
+                "float32_gradient_accumulation": accum,
+                "four_micro_batches_per_optimizer_step": {"ms_per_micro_batch": round((sp_h + 3 * ms_p) / 4, 4),
+                                                          "speedup_vs_dense": round(de_h / ((sp_h + 3 * ms_p) / 4), 4)}}
+
     # ================= headline workload ===========================================================================
     M = args.M
     hw = Workload(args.workload, args.zero_fraction, M, args.router)
@@ -398,6 +439,8 @@ def main():
     # ================= the other configurations, stand-alone kernels, micro-benchmarks =============================
     configs, kernels, gemm24, venom, router, fp8_bench, wide, router_step, fp8_step, other_mode = None, None, None, None, None, None, None, None, None, None
     micro = None
+    if args.headline_only and args.micro_batches:
+        micro = micro_section(hw, max(3, min(args.steps, 10)), max(1, min(args.warmup, 2)), 0.5 * (res["ms_sparse"] + res["ms_sparse2"]), 0.5 * (res["ms_dense"] + res["ms_dense2"]))
     if args.headline_only and args.fp8:
         fp8_step = fp8_section(hw, max(3, min(args.steps, 10)), max(1, min(args.warmup, 2)), 0.5 * (res["ms_sparse"] + res["ms_sparse2"]), 0.5 * (res["ms_dense"] + res["ms_dense2"]))
     if not args.headline_only and not args.router and M == 8:
@@ -415,43 +458,7 @@ def main():
             other_mode = {"mode": "hard" if other == sffn.MODE_HARD else "soft", "ms_per_step": round(timed(run_alt, esteps), 4)}
             del alt
             free()
-        # Section 3.4: a weight is converted to 2:4 once per optimizer step and the cost is amortised over the micro-batches that pass through
-        # the layer in between (pipeline parallelism / gradient accumulation).  SFFN_FLAG_WEIGHTS_PACKED = a micro-batch after the first: both
-        # pruning passes skipped, same outputs.  Reported beside the headline, which always includes the pruning passes.
-        if not hw.router:
-            sp_h, de_h = 0.5 * (res["ms_sparse"] + res["ms_sparse2"]), 0.5 * (res["ms_dense"] + res["ms_dense2"])
-            run_packed = lambda: hw.step(hw.X, hw.W1, hw.W2, hw.b1, hw.dY, weights_packed=True)
-            hw.sparse_step()
-            for _ in range(ewarm):
-                run_packed()
-            ms_p = timed(run_packed, esteps)
-            split_ms = None
-            if not hw.moe:      # Alg. 1 and Alg. 2 as separate calls (ffn_sparse_forward / ffn_sparse_backward): the step's launches in two halves
-                run_f = lambda: hw.step.forward(hw.X, hw.W1, hw.W2, hw.b1)
-                run_b = lambda: hw.step.backward(hw.W1, hw.dY)
-                run_f(); run_b()
-                split_ms = {"forward_ms": round(timed(run_f, esteps), 4), "backward_ms": round(timed(run_b, esteps), 4)}
-            accum = None
-            if not hw.moe:      # weight gradients summed over the micro-batches in float32: inside the weight-gradient GEMMs' epilogues
-                                # (SFFN_FLAG_DW_FP32_ACCUMULATE) against bf16 outputs + one add pass per weight in the framework
-                acc_step = sffn.FfnStep(hw.T, hw.D, hw.F, mode, M=M, lean=True, dw_fp32=True)
-                main1, main2 = torch.zeros_like(acc_step.dW1), torch.zeros_like(acc_step.dW2)
-                run_fused = lambda: acc_step(hw.X, hw.W1, hw.W2, hw.b1, hw.dY, weights_packed=True)
-
-                def run_separate():
-                    _, _, g1, g2 = hw.step(hw.X, hw.W1, hw.W2, hw.b1, hw.dY, weights_packed=True)
-                    main1.add_(g1)
-                    main2.add_(g2)
-                acc_step(hw.X, hw.W1, hw.W2, hw.b1, hw.dY)
-                run_fused(); run_separate()
-                accum = {"fused_into_the_weight_gradient_gemms_ms": round(timed(run_fused, esteps), 4),
-                         "bf16_outputs_plus_add_passes_ms": round(timed(run_separate, esteps), 4)}
-                del acc_step, main1, main2
-                free()
-            micro = {"weights_packed_ms_per_micro_batch": round(ms_p, 4), "speedup_vs_dense": round(de_h / ms_p, 4), "separate_calls": split_ms,
-                     "float32_gradient_accumulation": accum,
-                     "four_micro_batches_per_optimizer_step": {"ms_per_micro_batch": round((sp_h + 3 * ms_p) / 4, 4),
-                                                               "speedup_vs_dense": round(de_h / ((sp_h + 3 * ms_p) / 4), 4)}}
+        micro = micro_section(hw, esteps, ewarm, 0.5 * (res["ms_sparse"] + res["ms_sparse2"]), 0.5 * (res["ms_dense"] + res["ms_dense2"]))
         fp8_step = fp8_section(hw, esteps, ewarm, 0.5 * (res["ms_sparse"] + res["ms_sparse2"]), 0.5 * (res["ms_dense"] + res["ms_dense2"]))
         # configs[3]'s sweep of the ReLU zero fraction: same tensors, only the bias shifts
         if hw.name == "70b":
