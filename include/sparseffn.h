@@ -375,7 +375,8 @@ int ffn_sparse_step_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* s
  *   backward = Alg. 2, eqs. (4)-(8): dY -> dX, dW1, dW2.  The bf16 form reads the dense W1 in place (eq. (7)); the fp8 form reads the
  *              codes of W1 that its forward call wrote and takes no weight argument.
  * The one-call step's workspace is three regions with different lifetimes, and these calls take them as three DEVICE buffers
- * (256-byte aligned; sizes from sffn_buffer_sizes / sffn_fp8_buffer_sizes, which fill the *_bytes fields and clear the pointers):
+ * (256-byte aligned, not overlapping: SFFN_EINVAL otherwise; sizes from sffn_buffer_sizes / sffn_fp8_buffer_sizes, which fill the
+ * *_bytes fields and clear the pointers):
  *   scratch  nothing in it outlives a call: every layer and micro-batch on a stream can hand over the same buffer;
  *   saved    written by forward, read by backward: what Alg. 2 line 1 saves (y2's metadata and column offsets, y1 at y2's kept slots, X.T,
  *            the compacted y2v.T).  One per layer and micro-batch in flight; the caller keeps it untouched between the two calls;

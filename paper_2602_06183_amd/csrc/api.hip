@@ -69,6 +69,13 @@ inline int place_regions(const sffn_buffers* buf, void* workspace, size_t ws_byt
     if (!buf->scratch || !buf->saved || !buf->weights) return SFFN_EWORKSPACE;
     if (buf->scratch_bytes < scratch_end || buf->saved_bytes < saved_end - scratch_end || buf->weights_bytes < total - saved_end) return SFFN_EWORKSPACE;
     if ((reinterpret_cast<uintptr_t>(buf->scratch) | reinterpret_cast<uintptr_t>(buf->saved) | reinterpret_cast<uintptr_t>(buf->weights)) & 255u) return SFFN_EINVAL;
+    {   // the three regions must not overlap (one allocation carved into three consecutive pieces is fine)
+        const uintptr_t lo[3] = {reinterpret_cast<uintptr_t>(buf->scratch), reinterpret_cast<uintptr_t>(buf->saved), reinterpret_cast<uintptr_t>(buf->weights)};
+        const size_t len[3] = {scratch_end, saved_end - scratch_end, total - saved_end};
+        for (int i = 0; i < 3; ++i)
+            for (int j = i + 1; j < 3; ++j)
+                if (lo[i] < lo[j] + len[j] && lo[j] < lo[i] + len[i]) return SFFN_EINVAL;
+    }
     r->scratch = (unsigned char*)buf->scratch; r->saved = (unsigned char*)buf->saved; r->weights = (unsigned char*)buf->weights;
     return SFFN_OK;
 }
@@ -528,7 +535,7 @@ int run_fp8_step(const sffn_cfg* cfg, const sffn_fp8_scales* sc, int n_experts, 
     Regions rg;
     {
         const int rc = place_regions(buf, workspace, ws_bytes, L.scratch_end, L.saved_end, L.total, &rg);
-        REQUIRE(rc != SFFN_EINVAL, SFFN_EINVAL, "ffn_sparse_forward_fp8 / ffn_sparse_backward_fp8: the three buffers must be 256-byte aligned");
+        REQUIRE(rc != SFFN_EINVAL, SFFN_EINVAL, "ffn_sparse_forward_fp8 / ffn_sparse_backward_fp8: the three buffers must be 256-byte aligned and must not overlap");
         REQUIRE(rc == SFFN_OK, SFFN_EWORKSPACE, "ffn_sparse_step_fp8: workspace missing or too small (sffn_fp8_workspace_bytes)");
     }
     hipStream_t s = (hipStream_t)stream;
@@ -1035,7 +1042,7 @@ static int run_step(const sffn_cfg* cfg, int n_experts, const int64_t* seg, cons
     Regions rg;
     {
         const int rc = place_regions(buf, workspace, ws_bytes, L.scratch_end, L.saved_end, L.total, &rg);
-        REQUIRE(rc != SFFN_EINVAL, SFFN_EINVAL, "ffn_sparse_forward / ffn_sparse_backward: the three buffers must be 256-byte aligned");
+        REQUIRE(rc != SFFN_EINVAL, SFFN_EINVAL, "ffn_sparse_forward / ffn_sparse_backward: the three buffers must be 256-byte aligned and must not overlap");
         REQUIRE(rc == SFFN_OK, SFFN_EWORKSPACE, "ffn_sparse_step: workspace missing or too small");
     }
     GemmGroup g;                                    // g.n = 0: plain step

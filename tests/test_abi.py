@@ -81,18 +81,24 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     assert min(sizes.scratch_bytes, sizes.saved_bytes, sizes.weights_bytes) > 0 and sizes.scratch is None
     assert lib.sffn_buffer_sizes(ctypes.byref(bad), 1, ctypes.byref(sizes)) == -1
     assert lib.sffn_buffer_sizes(ctypes.byref(cfg), 1, ctypes.byref(sizes)) == 0
-    good = binding._Buffers(0x1000, sizes.scratch_bytes, 0x2000, sizes.saved_bytes, 0x3000, sizes.weights_bytes)
-    short = binding._Buffers(0x1000, sizes.scratch_bytes, 0x2000, sizes.saved_bytes - 256, 0x3000, sizes.weights_bytes)
-    skew = binding._Buffers(0x1000, sizes.scratch_bytes, 0x2010, sizes.saved_bytes, 0x3000, sizes.weights_bytes)
+    far = 1 << 40               # (fake device addresses, far enough apart for any of these sizes)
+    good = binding._Buffers(far, sizes.scratch_bytes, 2 * far, sizes.saved_bytes, 3 * far, sizes.weights_bytes)
+    short = binding._Buffers(far, sizes.scratch_bytes, 2 * far, sizes.saved_bytes - 256, 3 * far, sizes.weights_bytes)
+    skew = binding._Buffers(far, sizes.scratch_bytes, 2 * far + 16, sizes.saved_bytes, 3 * far, sizes.weights_bytes)
     assert lib.ffn_sparse_forward(ctypes.byref(cfg), fake, fake, fake, fake, fake, None, None) == -1
     assert lib.ffn_sparse_forward(ctypes.byref(cfg), fake, fake, fake, fake, fake, ctypes.byref(short), None) == -3
     assert lib.ffn_sparse_forward(ctypes.byref(cfg), fake, fake, fake, fake, fake, ctypes.byref(skew), None) == -1
+    overlap = binding._Buffers(far, sizes.scratch_bytes, far + sizes.scratch_bytes - 256, sizes.saved_bytes, 3 * far, sizes.weights_bytes)
+    carved = binding._Buffers(far, sizes.scratch_bytes, far + sizes.scratch_bytes, sizes.saved_bytes, far + sizes.scratch_bytes + sizes.saved_bytes, sizes.weights_bytes)
+    assert lib.ffn_sparse_forward(ctypes.byref(cfg), fake, fake, fake, fake, fake, ctypes.byref(overlap), None) == -1
+    assert lib.ffn_sparse_forward(ctypes.byref(cfg), None, fake, fake, fake, fake, ctypes.byref(carved), None) == -1        # (buffers accepted: the null X is what fails)
+    assert "null pointer" in lib.sffn_last_error().decode()
     assert lib.ffn_sparse_forward(ctypes.byref(cfg), None, fake, fake, fake, fake, ctypes.byref(good), None) == -1
     assert lib.ffn_sparse_backward(ctypes.byref(cfg), fake, fake, fake, fake, fake, ctypes.byref(short), None) == -3
     assert lib.ffn_sparse_backward(ctypes.byref(cfg), fake, None, fake, fake, fake, ctypes.byref(good), None) == -1
     wide_unfused = binding._Cfg(512, 256, 1024, 64, 16, 0, 2)
     assert lib.sffn_buffer_sizes(ctypes.byref(wide_unfused), 1, ctypes.byref(sizes)) == 0
-    big = binding._Buffers(0x1000, 1 << 40, 0x2000, 1 << 40, 0x3000, 1 << 40)
+    big = binding._Buffers(far, far, 2 * far, far, 3 * far, far)
     assert lib.ffn_sparse_backward(ctypes.byref(wide_unfused), fake, fake, fake, fake, fake, ctypes.byref(big), None) == -2   # unfused path
     assert lib.ffn_sparse_forward_grouped(ctypes.byref(cfg), 2, None, fake, fake, fake, fake, fake, ctypes.byref(big), None) == -1
     assert lib.ffn_sparse_backward_grouped(ctypes.byref(cfg), 2, None, fake, fake, fake, fake, fake, ctypes.byref(big), None) == -1
@@ -111,8 +117,8 @@ def test_bad_arguments_are_rejected_without_touching_the_gpu():
     f8sizes = binding._Buffers()
     assert lib.sffn_fp8_buffer_sizes(ctypes.byref(cfg), 1, ctypes.byref(f8sizes)) == 0
     assert f8sizes.scratch_bytes + f8sizes.saved_bytes + f8sizes.weights_bytes == lib.sffn_fp8_workspace_bytes(ctypes.byref(cfg))
-    f8good = binding._Buffers(0x1000, f8sizes.scratch_bytes, 0x2000, f8sizes.saved_bytes, 0x3000, f8sizes.weights_bytes)
-    f8short = binding._Buffers(0x1000, f8sizes.scratch_bytes, 0x2000, f8sizes.saved_bytes, 0x3000, f8sizes.weights_bytes - 256)
+    f8good = binding._Buffers(far, f8sizes.scratch_bytes, 2 * far, f8sizes.saved_bytes, 3 * far, f8sizes.weights_bytes)
+    f8short = binding._Buffers(far, f8sizes.scratch_bytes, 2 * far, f8sizes.saved_bytes, 3 * far, f8sizes.weights_bytes - 256)
     assert lib.ffn_sparse_forward_fp8(ctypes.byref(cfg), ctypes.byref(sc), None, fake, fake, fake, fake, ctypes.byref(f8good), None, None) == -1
     assert lib.ffn_sparse_forward_fp8(ctypes.byref(cfg), ctypes.byref(sc), fake, fake, fake, fake, fake, ctypes.byref(f8short), None, None) == -3
     assert lib.ffn_sparse_backward_fp8(ctypes.byref(cfg), ctypes.byref(sc), fake, fake, fake, None, ctypes.byref(f8good), None, None) == -1
