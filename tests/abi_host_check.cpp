@@ -54,6 +54,33 @@ int main() {
     EXPECT(ffn_sparse_step_grouped(&cfg, 2, seg_ok, fake, fake, fake, fakef, fake, fake, fake, fake, fake, ws, 16, nullptr), SFFN_EWORKSPACE);
     EXPECT(ffn_sparse_step_grouped(&cfg, 65, seg_many, fake, fake, fake, fakef, fake, fake, fake, fake, fake, ws, (size_t)1 << 40, nullptr), SFFN_EINVAL);
     EXPECT(ffn_sparse_step_grouped(&cfg, 2, nullptr, fake, fake, fake, fakef, fake, fake, fake, fake, fake, ws, (size_t)1 << 40, nullptr), SFFN_EINVAL);
+    // Alg. 1 / Alg. 2 as separate calls on three buffers: sizes, alignment, overlap, the pointers each half needs, the flags
+    sffn_buffers sz;
+    EXPECT(sffn_buffer_sizes(&cfg, 1, &sz), SFFN_OK);
+    if (sz.scratch_bytes + sz.saved_bytes + sz.weights_bytes != sffn_workspace_bytes(&cfg) || sz.scratch != nullptr) { printf("FAIL: buffer sizes\n"); ++failures; }
+    EXPECT(sffn_buffer_sizes(&cfg, 1, nullptr), SFFN_EINVAL);
+    const uintptr_t far = (uintptr_t)1 << 40;
+    sffn_buffers good = {(void*)far, sz.scratch_bytes, (void*)(2 * far), sz.saved_bytes, (void*)(3 * far), sz.weights_bytes};
+    sffn_buffers shorter = good, crossing = good, skewed = good;
+    shorter.weights_bytes -= 256;
+    crossing.saved = (void*)(far + sz.scratch_bytes - 256);
+    skewed.scratch = (void*)(far + 64);
+    EXPECT(ffn_sparse_forward(&cfg, fake, fake, fake, fakef, fake, &shorter, nullptr), SFFN_EWORKSPACE);
+    EXPECT(ffn_sparse_forward(&cfg, fake, fake, fake, fakef, fake, &crossing, nullptr), SFFN_EINVAL);
+    EXPECT(ffn_sparse_forward(&cfg, fake, fake, fake, fakef, fake, &skewed, nullptr), SFFN_EINVAL);
+    EXPECT(ffn_sparse_forward(&cfg, fake, fake, nullptr, fakef, fake, &good, nullptr), SFFN_EINVAL);
+    EXPECT(ffn_sparse_backward(&cfg, fake, fake, fake, fake, nullptr, &good, nullptr), SFFN_EINVAL);
+    EXPECT(ffn_sparse_backward(&cfg, fake, fake, fake, fake, fake, nullptr, nullptr), SFFN_EINVAL);
+    cfg.flags = 64;
+    EXPECT(ffn_sparse_forward(&cfg, fake, fake, fake, fakef, fake, &good, nullptr), SFFN_EINVAL);                       // unknown flag
+    cfg.flags = 0;
+    sffn_buffers sz8;
+    EXPECT(sffn_fp8_buffer_sizes(&cfg, 1, &sz8), SFFN_OK);
+    sffn_fp8_scales sc8 = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
+    sffn_buffers good8 = {(void*)far, sz8.scratch_bytes, (void*)(2 * far), sz8.saved_bytes, (void*)(3 * far), sz8.weights_bytes};
+    EXPECT(ffn_sparse_backward_fp8(&cfg, &sc8, fake, fake, fake, nullptr, &good8, nullptr, nullptr), SFFN_EINVAL);
+    good8.saved_bytes -= 256;
+    EXPECT(ffn_sparse_forward_fp8(&cfg, &sc8, fake, fake, fake, fakef, fake, &good8, nullptr, nullptr), SFFN_EWORKSPACE);
     sffn_cfg big = cfg;
     big.T = 2048; big.D = 1024; big.F = 4096;
     EXPECT(ffn_sparse_step_noalloc(&big, fake, fake, fake, fakef, fake, fake, fake, fake, fake, nullptr), SFFN_EWORKSPACE);
