@@ -85,3 +85,24 @@ def test_fp8_step_replays_in_a_graph(wgrad_fp8, M):
     a, b = sffn.FfnStepFp8(T, D, F, sc, wgrad_fp8=wgrad_fp8, M=M), sffn.FfnStepFp8(T, D, F, sc, wgrad_fp8=wgrad_fp8, M=M)
     call = lambda step: (lambda d: step(d["X"], d["W1"], d["W2"], d["b1"], d["dY"]))
     _replay_against_eager(lambda seed: make_ffn_inputs(T, D, F, seed=seed), call(a), call(b), ("X", "W1", "W2", "b1", "dY"))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("M", [8, 16])
+def test_split_calls_with_gradient_accumulation_replay_in_a_graph(M):
+    """What a captured training iteration holds for one layer: the forward call, later the backward call that adds the weight gradients to
+    float32 buffers (SFFN_FLAG_DW_FP32_ACCUMULATE), on a shared scratch buffer.  The helper zeroes the outputs before each replay, so every
+    replay must leave exactly what an eager one-call step leaves in zeroed buffers."""
+    T, D, F = 256, 256, 1024
+    scratch = torch.empty((sffn.buffer_sizes(T, D, F, M=M)["scratch"],), dtype=torch.uint8, device="cuda")
+    a, b = sffn.FfnStep(T, D, F, M=M, scratch=scratch, dw_fp32=True), sffn.FfnStep(T, D, F, M=M, dw_fp32=True)
+
+    def captured(d):
+        y3 = a.forward(d["X"], d["W1"], d["W2"], d["b1"])
+        return (y3,) + tuple(a.backward(d["W1"], d["dY"]))
+
+    def eager(d):
+        b.dW1.zero_()
+        b.dW2.zero_()
+        return b(d["X"], d["W1"], d["W2"], d["b1"], d["dY"])
+    _replay_against_eager(lambda seed: make_ffn_inputs(T, D, F, seed=seed), captured, eager, ("X", "W1", "W2", "b1", "dY"))
