@@ -446,3 +446,26 @@ def _meta_cols(meta, blocks):
     """The metadata nibbles of the given column blocks, repacked two per byte ([T, len(blocks) / 2])."""
     nib = np.stack([meta & 0xF, meta >> 4], axis=-1).reshape(meta.shape[0], -1)[:, blocks]
     return (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+
+
+def test_full_size_micro_batch_modes_are_bit_identical():
+    """The 70B-scale layer in the modes a training loop uses: the second micro-batch on the packed weights of the first
+    (SFFN_FLAG_WEIGHTS_PACKED) through the separate forward / backward calls, weight gradients added to float32 buffers
+    (SFFN_FLAG_DW_FP32_ACCUMULATE).  Checked against the plain one-call step, which the tests above check against the oracle: Y3 and dX
+    bit for bit; from zero, the float32 buffers round to the plain step's bf16 dW1 / dW2 bit for bit."""
+    T, D, F = CONFIGS["70b"]
+    inp = make_ffn_inputs(T, D, F, seed=0)
+    dev = {k: to_dev(v) for k, v in inp.items()}
+    plain = sffn.FfnStep(T, D, F, lean=True)
+    want = [to_bits(t).copy() for t in plain(dev["X"], dev["W1"], dev["W2"], dev["b1"], dev["dY"])]
+    del plain
+    torch.cuda.empty_cache()
+    step = sffn.FfnStep(T, D, F, lean=True, dw_fp32=True)
+    X0 = torch.flip(dev["X"], (0,)).contiguous()
+    step.forward(X0, dev["W1"], dev["W2"], dev["b1"])                        # micro-batch 0 packs the weights (its gradients are not taken)
+    y3 = to_bits(step.forward(dev["X"], dev["W1"], dev["W2"], dev["b1"], weights_packed=True))
+    assert np.array_equal(y3, want[0])
+    dX, dW1, dW2 = step.backward(dev["W1"], dev["dY"])
+    assert np.array_equal(to_bits(dX), want[1])
+    assert np.array_equal(to_bits(dW1.to(torch.bfloat16)), want[2])
+    assert np.array_equal(to_bits(dW2.to(torch.bfloat16)), want[3])
