@@ -309,7 +309,8 @@ int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint1
 
 /* The router's step as two calls (forward: Alg. 1 with Alg. 3 as the sparsifier, eqs. (1)-(3); backward: Alg. 2, eqs. (4)-(8)), for a
  * training loop in which other layers run in between.  Same launches, order and bits as the one-call forms.  The two halves meet in
- * `workspace`, which the caller keeps untouched between them (one per layer in flight); the backward call takes the same seg_offsets
+ * `workspace`, which the caller keeps untouched between them (one per layer in flight; the backward call consumes what the forward
+ * call left, so each forward call is followed by one backward call); the backward call takes the same seg_offsets
  * and perm as the forward call (ffn_router_full_backward reads the routing that ffn_router_full_forward left in the workspace), and
  * W1 again: eq. (7) reads the dense W1. */
 int ffn_router_forward(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* X,
@@ -379,7 +380,8 @@ int ffn_sparse_step_grouped(const sffn_cfg* cfg, int n_experts, const int64_t* s
  * *_bytes fields and clear the pointers):
  *   scratch  nothing in it outlives a call: every layer and micro-batch on a stream can hand over the same buffer;
  *   saved    written by forward, read by backward: what Alg. 2 line 1 saves (y2's metadata and column offsets, y1 at y2's kept slots, X.T,
- *            the compacted y2v.T).  One per layer and micro-batch in flight; the caller keeps it untouched between the two calls;
+ *            the compacted y2v.T).  One per layer and micro-batch in flight; the caller keeps it untouched between the two calls.
+ *            The backward call consumes it (eq. (6)'s results take the place of y2's in part of it): one backward call per forward call;
  *   weights  written by a forward call without SFFN_FLAG_WEIGHTS_PACKED (both packed weights, W2.T; fp8: W1's codes too), read by that
  *            call, by its backward call and by every later call with the flag.  One per layer, good until the weights change.
  * The library cannot check what the buffers hold.  Arguments, shapes, alignment, error codes otherwise: those of the one-call entry
