@@ -69,7 +69,7 @@ def main():
                     help="time the neuron-level router's training step (Section 3.3: ffn_router_full_step = routing + grouped step, M / 4 experts) instead of the magnitude-based V:N:M step")
     ap.add_argument("--settle-s", type=float, default=None,
                     help="seconds of untimed work (both steps alternating) before the warm-up, so that the timed region sees steady-state clocks "
-                         "(default 10; 0 with --headline-only, whose runs are traced by a profiler)")
+                         "(default 20; 0 with --headline-only, whose runs are traced by a profiler)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--headline-only", action="store_true", help="skip the other configurations, the stand-alone kernels and the micro-benchmarks (profiling runs)")
     ap.add_argument("--fp8", action="store_true", help="with --headline-only: also run the fp8 step (both weight-gradient variants) at the headline shape (profiling runs)")
@@ -79,7 +79,7 @@ def main():
                     help="also run a plain 1 GiB device copy three times (reference kernel for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.settle_s is None:
-        args.settle_s = 0.0 if args.headline_only else 10.0
+        args.settle_s = 0.0 if args.headline_only else 20.0
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the step shards by tokens; no multi-GPU path is built). Use --gpus 1.")
 
@@ -507,8 +507,12 @@ def main():
         for m in (8, 16, 32, 64):
             w = Workload("1b", 0.90, m, router=True, host=host_1b)
             r = w.measure(esteps, ewarm)
+            run_rp = lambda: w.step.full(w.means, w.X, w.W1, w.W2, w.b1, w.dY, weights_packed=True)     # a later micro-batch: no weight preparation
+            run_rp()
+            ms_rp = timed(run_rp, esteps)
             router_step["64:2:%d" % m] = {"experts": m // 4, "ms_per_step": round(r["ms_sparse"], 4), "dense_ms_per_step": round(r["ms_dense"], 4),
-                                          "speedup_vs_dense": round(r["ms_dense"] / r["ms_sparse"], 4)}
+                                          "speedup_vs_dense": round(r["ms_dense"] / r["ms_sparse"], 4),
+                                          "weights_packed_ms_per_micro_batch": round(ms_rp, 4), "weights_packed_speedup_vs_dense": round(r["ms_dense"] / ms_rp, 4)}
             del w
             free()
 

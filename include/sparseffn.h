@@ -76,8 +76,8 @@ typedef struct sffn_cfg {
  * by the unfused path.  With the flag those regions of the workspace are empty (0 bytes): sffn_workspace_bytes() and the layouts
  * depend on it.  The fp8 steps have the same flag (w1 / w2t codes and metadata; at M = 8 y2_codes). */
 #define SFFN_FLAG_LEAN 8
-/* ffn_sparse_step, ffn_sparse_step_grouped, ffn_sparse_step_fp8, ffn_sparse_step_fp8_grouped (not the unfused path, not the router
- * steps: SFFN_EUNSUPPORTED there): the weights are already packed.  Section 3.4 notes that the conversion of a weight to 2:4 is paid
+/* ffn_sparse_step, ffn_sparse_step_grouped, ffn_sparse_step_fp8, ffn_sparse_step_fp8_grouped, the router's steps (not the unfused
+ * path: SFFN_EUNSUPPORTED there): the weights are already packed.  Section 3.4 notes that the conversion of a weight to 2:4 is paid
  * once per optimizer step and amortised over the micro-batches that pass through the layer before the weights change.  The caller
  * promises that the previous call on this workspace ran without this flag on the same cfg (apart from this flag), W1 and W2 (fp8: and
  * the same scales w1, w2), and that nothing else has written the workspace since; the step then skips Alg. 1 line 4 and Alg. 2 line 2
@@ -307,22 +307,23 @@ int ffn_router_full_step(const sffn_cfg* cfg, const uint16_t* means, const uint1
                          const uint16_t* W2, const float* b1, const uint16_t* dY, uint16_t* Y3, uint16_t* dX,
                          uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
 
-/* The router's step as two calls (forward: Alg. 1 with Alg. 3 as the sparsifier, eqs. (1)-(3); backward: Alg. 2, eqs. (4)-(8)), for a
- * training loop in which other layers run in between.  Same launches, order and bits as the one-call forms.  The two halves meet in
- * `workspace`, which the caller keeps untouched between them (one per layer in flight; the backward call consumes what the forward
- * call left, so each forward call is followed by one backward call); the backward call takes the same seg_offsets
- * and perm as the forward call (ffn_router_full_backward reads the routing that ffn_router_full_forward left in the workspace), and
- * W1 again: eq. (7) reads the dense W1. */
+/* The router's step as two calls (forward: Alg. 1 with Alg. 3 as the sparsifier, eqs. (1)-(3), and ALL of the weight preparation,
+ * Alg. 2 line 2 and the experts' slices of W2 and W1.T included; backward: Alg. 2, eqs. (4)-(8)), for a training loop in which other
+ * layers run in between.  Same kernels and bits as the one-call forms.  The two halves meet in `workspace`, which the caller keeps
+ * untouched between them (one per layer in flight; the backward call consumes what the forward call left, so each forward call is
+ * followed by one backward call); the backward call takes the same seg_offsets and perm as the forward call
+ * (ffn_router_full_backward reads the routing that ffn_router_full_forward left in the workspace) and no weights.
+ * SFFN_FLAG_WEIGHTS_PACKED (one-call and forward forms): the five weight-preparation launches are skipped and the call reads what
+ * the previous call on this workspace prepared from the same W1, W2 (the caller's promise, as for ffn_sparse_step). */
 int ffn_router_forward(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* X,
                        const uint16_t* W1, const uint16_t* W2, const float* b1, uint16_t* Y3, void* workspace, size_t ws_bytes,
                        void* stream);
-int ffn_router_backward(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* W1,
-                        const uint16_t* dY, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes,
-                        void* stream);
+int ffn_router_backward(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* dY, uint16_t* dX,
+                        uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
 int ffn_router_full_forward(const sffn_cfg* cfg, const uint16_t* means, const uint16_t* X, const uint16_t* W1,
                             const uint16_t* W2, const float* b1, uint16_t* Y3, void* workspace, size_t ws_bytes, void* stream);
-int ffn_router_full_backward(const sffn_cfg* cfg, const uint16_t* W1, const uint16_t* dY, uint16_t* dX, uint16_t* dW1,
-                             uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream);
+int ffn_router_full_backward(const sffn_cfg* cfg, const uint16_t* dY, uint16_t* dX, uint16_t* dW1, uint16_t* dW2,
+                             void* workspace, size_t ws_bytes, void* stream);
 
 /* Alg. 1 + Alg. 2, one call: X [T,D], W1 [F,D], W2 [D,F], b1 fp32 [F] or NULL, dY [T,D] ->
  * Y3 [T,D], dX [T,D], dW1 [F,D], dW2 [D,F]; intermediates land in `workspace` at the offsets of

@@ -129,9 +129,9 @@ def load():
     lib.ffn_sparse_forward_fp8_grouped.argtypes = [cfgp, scp, i32, segp] + [p] * 5 + [bufp, p, p]
     lib.ffn_sparse_backward_fp8_grouped.argtypes = [cfgp, scp, i32, segp] + [p] * 4 + [bufp, p, p]
     lib.ffn_router_forward.argtypes = [cfgp, segp] + [p] * 6 + [p, sz, p]
-    lib.ffn_router_backward.argtypes = [cfgp, segp] + [p] * 6 + [p, sz, p]
+    lib.ffn_router_backward.argtypes = [cfgp, segp] + [p] * 5 + [p, sz, p]
     lib.ffn_router_full_forward.argtypes = [cfgp] + [p] * 6 + [p, sz, p]
-    lib.ffn_router_full_backward.argtypes = [cfgp] + [p] * 5 + [p, sz, p]
+    lib.ffn_router_full_backward.argtypes = [cfgp] + [p] * 4 + [p, sz, p]
     lib.sffn_dense_sqrelu.argtypes = [p, p, i64, p]
     lib.sffn_dense_dsqrelu.argtypes = [p, p, p, i64, p]
     lib.sffn_profile_enable.argtypes = [i32]
@@ -928,7 +928,7 @@ class FfnRouterStep:
         _want(who + ": b1", b1, (F,), _F32, optional=True)
         _want(who + ": dY", dY, (T, D), _BF16)
 
-    def __call__(self, route, X, W1, W2, b1, dY):
+    def __call__(self, route, X, W1, W2, b1, dY, weights_packed=False):
         """route: the dict venom_route returned for X."""
         E = self.M // 4
         self._want_inputs("ffn_router_step", X, W1, W2, b1, dY)
@@ -936,20 +936,20 @@ class FfnRouterStep:
         if len(route["seg"]) != E + 1:
             raise SffnError("ffn_router_step: seg must hold M / 4 + 1 run offsets")
         seg_arr = (ctypes.c_int64 * (E + 1))(*[int(v) for v in route["seg"]])
-        _check(load().ffn_router_step(ctypes.byref(self.cfg), seg_arr, _ptr(route["perm"]), _ptr(X), _ptr(W1),
+        _check(load().ffn_router_step(ctypes.byref(_cfg_with(self.cfg, weights_packed)), seg_arr, _ptr(route["perm"]), _ptr(X), _ptr(W1),
                                       _ptr(W2), _ptr(b1), _ptr(dY), _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2),
                                       _ptr(self.ws), self.layout["total"], _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
 
-    def full(self, means, X, W1, W2, b1, dY):
+    def full(self, means, X, W1, W2, b1, dY, weights_packed=False):
         """Routing included (ffn_router_full_step): no read-back of the run offsets, nothing but launches on the stream."""
         self._want_inputs("ffn_router_full_step", X, W1, W2, b1, dY)
         _want("ffn_router_full_step: means", means, (self.M // 4, self.D), _BF16)
-        _check(load().ffn_router_full_step(ctypes.byref(self.cfg), _ptr(means), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY),
+        _check(load().ffn_router_full_step(ctypes.byref(_cfg_with(self.cfg, weights_packed)), _ptr(means), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(dY),
                                            _ptr(self.Y3), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2), _ptr(self.ws), self.ws_bytes, _stream()))
         return self.Y3, self.dX, self.dW1, self.dW2
 
-    def forward(self, route, X, W1, W2, b1):
+    def forward(self, route, X, W1, W2, b1, weights_packed=False):
         """Alg. 1 with Alg. 3 as the sparsifier (ffn_router_forward); route: the dict venom_route returned for X."""
         T, D, F, E = self.T, self.D, self.F, self.M // 4
         _want("ffn_router_forward: X", X, (T, D), _BF16)
@@ -960,22 +960,21 @@ class FfnRouterStep:
         if len(route["seg"]) != E + 1:
             raise SffnError("ffn_router_forward: seg must hold M / 4 + 1 run offsets")
         seg_arr = (ctypes.c_int64 * (E + 1))(*[int(v) for v in route["seg"]])
-        _check(load().ffn_router_forward(ctypes.byref(self.cfg), seg_arr, _ptr(route["perm"]), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(self.Y3),
+        _check(load().ffn_router_forward(ctypes.byref(_cfg_with(self.cfg, weights_packed)), seg_arr, _ptr(route["perm"]), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(self.Y3),
                                          _ptr(self.ws), self.layout["total"], _stream()))
         return self.Y3
 
-    def backward(self, route, W1, dY):
+    def backward(self, route, dY):
         """Alg. 2 (ffn_router_backward) on what the last forward() left, with the same route."""
         E = self.M // 4
-        _want("ffn_router_backward: W1", W1, (self.F, self.D), _BF16)
         _want("ffn_router_backward: dY", dY, (self.T, self.D), _BF16)
         _want("ffn_router_backward: perm", route["perm"], (self.rows,), _I32)
         seg_arr = (ctypes.c_int64 * (E + 1))(*[int(v) for v in route["seg"]])
-        _check(load().ffn_router_backward(ctypes.byref(self.cfg), seg_arr, _ptr(route["perm"]), _ptr(W1), _ptr(dY), _ptr(self.dX), _ptr(self.dW1),
+        _check(load().ffn_router_backward(ctypes.byref(self.cfg), seg_arr, _ptr(route["perm"]), _ptr(dY), _ptr(self.dX), _ptr(self.dW1),
                                           _ptr(self.dW2), _ptr(self.ws), self.layout["total"], _stream()))
         return self.dX, self.dW1, self.dW2
 
-    def full_forward(self, means, X, W1, W2, b1):
+    def full_forward(self, means, X, W1, W2, b1, weights_packed=False):
         """Routing + Alg. 1 (ffn_router_full_forward); the routing stays in the workspace for full_backward()."""
         T, D, F = self.T, self.D, self.F
         _want("ffn_router_full_forward: X", X, (T, D), _BF16)
@@ -983,15 +982,14 @@ class FfnRouterStep:
         _want("ffn_router_full_forward: W2", W2, (D, F), _BF16)
         _want("ffn_router_full_forward: b1", b1, (F,), _F32, optional=True)
         _want("ffn_router_full_forward: means", means, (self.M // 4, D), _BF16)
-        _check(load().ffn_router_full_forward(ctypes.byref(self.cfg), _ptr(means), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(self.Y3),
+        _check(load().ffn_router_full_forward(ctypes.byref(_cfg_with(self.cfg, weights_packed)), _ptr(means), _ptr(X), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(self.Y3),
                                               _ptr(self.ws), self.ws_bytes, _stream()))
         return self.Y3
 
-    def full_backward(self, W1, dY):
+    def full_backward(self, dY):
         """Alg. 2 (ffn_router_full_backward) on the routing and the intermediates the last full_forward() left."""
-        _want("ffn_router_full_backward: W1", W1, (self.F, self.D), _BF16)
         _want("ffn_router_full_backward: dY", dY, (self.T, self.D), _BF16)
-        _check(load().ffn_router_full_backward(ctypes.byref(self.cfg), _ptr(W1), _ptr(dY), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2),
+        _check(load().ffn_router_full_backward(ctypes.byref(self.cfg), _ptr(dY), _ptr(self.dX), _ptr(self.dW1), _ptr(self.dW2),
                                                _ptr(self.ws), self.ws_bytes, _stream()))
         return self.dX, self.dW1, self.dW2
 

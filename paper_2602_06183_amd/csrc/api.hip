@@ -792,7 +792,7 @@ int venom_expert_matmul(const sffn_cfg* cfg, const int64_t* seg_offsets, const u
 namespace {
 struct RouterLayout {
     sffn_router_layout pub;
-    size_t xpt, xb, dypt, dyb, w1cv, w1cm, w1cvb, w1cmb, w2t, w2cv, w2cm, w2cvb, w2cmb, at, avb, amb, wcb, total;
+    size_t xpt, xb, dypt, dyb, w1cv, w1cm, w1cvb, w1cmb, w2t, w2cv, w2cm, w2cvb, w2cmb, at, avb, amb, w2e, w1et, total;
 };
 bool make_router_layout(const sffn_cfg* c, RouterLayout* L) {
     if (!c || c->T <= 0 || !mult64(c->D) || !mult64(c->F) || !vnm_ok(c->V, c->M)) return false;
@@ -810,7 +810,8 @@ bool make_router_layout(const sffn_cfg* c, RouterLayout* L) {
     L->w2cv = take(F * D); L->w2cm = take(F * D / 8); L->w2cvb = take(F * D); L->w2cmb = take(F * D / 8);
     L->at = take(rows * Kc * 2);
     L->avb = take(rows * Kc); L->amb = take(rows * Kc / 8);     // packed activation (y2, then dy1) in the blocked operand layout
-    L->wcb = take(F * D * 2);                                    // per expert: its slice of W2 (then of W1.T) as [D, Kc], blocked
+    L->w2e = take(F * D * 2);                                    // per expert: its slice of W2 as [D, Kc], blocked (eq. (3))
+    L->w1et = take(F * D * 2);                                   // per expert: its slice of W1.T as [D, Kc], blocked (eq. (7))
     L->total = off; L->pub.total = off;
     return true;
 }
@@ -836,14 +837,13 @@ static int run_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, cons
                            uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream, bool check_only = false, int phase = 3) {
     // phase: bit 0 = Alg. 1 with Alg. 3 as the sparsifier (forward pass), bit 1 = Alg. 2 (backward pass); the halves of a split call meet in the workspace
     const bool fwd = (phase & 1) != 0, bwd = (phase & 2) != 0;
-    REQUIRE(cfg && (seg_offsets || seg_dev) && perm && W1 && (!fwd || (X && W2 && Y3)) && (!bwd || (dY && dX && dW1 && dW2)), SFFN_EINVAL,
+    REQUIRE(cfg && (seg_offsets || seg_dev) && perm && (!fwd || (X && W1 && W2 && Y3)) && (!bwd || (dY && dX && dW1 && dW2)), SFFN_EINVAL,
             "ffn_router_step: null pointer");
     REQUIRE(vnm_ok(cfg->V, cfg->M), SFFN_EUNSUPPORTED, "ffn_router_step: only V=64 with M in {8, 16, 32, 64} is built");
     RouterLayout L;
     REQUIRE(make_router_layout(cfg, &L), SFFN_EINVAL, "ffn_router_step: T > 0, D and F positive multiples of 64, 4F/M a multiple of 64");
     REQUIRE(cfg->mode == SFFN_MODE_HARD || cfg->mode == SFFN_MODE_SOFT, SFFN_EINVAL, "ffn_router_step: unknown mode");
-    REQUIRE(!(cfg->flags & (SFFN_FLAG_WEIGHTS_PACKED | SFFN_FLAG_DW_FP32_ACCUMULATE)), SFFN_EUNSUPPORTED,
-            "ffn_router_step: SFFN_FLAG_WEIGHTS_PACKED and SFFN_FLAG_DW_FP32_ACCUMULATE are not built for the router's step");
+    REQUIRE(!(cfg->flags & SFFN_FLAG_DW_FP32_ACCUMULATE), SFFN_EUNSUPPORTED, "ffn_router_step: SFFN_FLAG_DW_FP32_ACCUMULATE is not built for the router's step");
     const int64_t T = cfg->T, D = cfg->D, F = cfg->F;
     const int M = cfg->M, E = M / 4;
     const int64_t Kc = 4 * F / M, rows = sffn_venom_rows(T, M);
@@ -884,12 +884,17 @@ static int run_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, cons
     uint16_t* w2t = (uint16_t*)(ws + L.w2t);
     uint16_t* w2cv = (uint16_t*)(ws + L.w2cv); uint8_t* w2cm = ws + L.w2cm; uint16_t* w2cvb = (uint16_t*)(ws + L.w2cvb); uint8_t* w2cmb = ws + L.w2cmb;
     uint16_t* at = (uint16_t*)(ws + L.at);
-    uint16_t* avb = (uint16_t*)(ws + L.avb); uint8_t* amb = ws + L.amb; uint16_t* wcb = (uint16_t*)(ws + L.wcb);
+    uint16_t* avb = (uint16_t*)(ws + L.avb); uint8_t* amb = ws + L.amb;
+    uint16_t* w2e = (uint16_t*)(ws + L.w2e); uint16_t* w1et = (uint16_t*)(ws + L.w1et);
+    uint16_t* dw2t = w2t;                               // eq. (5)'s transposed result: W2.T is only needed while the weights are prepared
+    // SFFN_FLAG_WEIGHTS_PACKED: the five weight-preparation launches (all in the forward half) are skipped; the workspace still holds
+    // what they wrote for the previous call (Section 3.4: weights are converted once per optimizer step)
+    const bool packed = (cfg->flags & SFFN_FLAG_WEIGHTS_PACKED) != 0;
 
     if (g_prof_on) { g_prof_n = 0; (void)hipEventRecord(g_prof_ev[0], s); }
     // ---- Alg. 1 with Alg. 3 as the sparsifier ---------------------------------------------------------------------
     if (fwd) STAGE(launch_transpose(X, rows, D, D, xpt, 0, xb, s, 1, 0, perm), "router/X[perm].T");     // permuted rows: transposed (eq. (8)) and blocked (eq. (1))
-    if (fwd) STAGE(launch_prune24_step(W1, F, D, D, 0, cfg->mode, w1cv, w1cm, w1cvb, w1cmb, nullptr, s, 1, M), "router/prune24(W1)");
+    if (fwd && !packed) STAGE(launch_prune24_step(W1, F, D, D, 0, cfg->mode, w1cv, w1cm, w1cvb, w1cmb, nullptr, s, 1, M), "router/prune24(W1)");
     if (fwd) STAGE(launch_venom_colidx(g1, rows, F / M, colidx, s), "router/colidx");
     if (fwd) {   // rows past the last run are padding that no contraction writes: one launch clears them in the five row-indexed outputs
         TailFill tf;
@@ -905,17 +910,20 @@ static int run_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, cons
         ep.mode = 3; ep.store_dense = 1; ep.vals = vals; ep.meta = meta; ep.perm = perm; ep.logM = logM; ep.v24 = avb; ep.m24 = amb;
         STAGE(launch_gemm_vnm_epilogue(w1cvb, w1cmb, xb, b1, Kc, rows, D, y1c, ep, s, &g1), "router/y1c+sqrelu+2:4");    // eqs. (1), (2), Section 2.3
     }
-    if (fwd) STAGE(launch_transpose(W2, D, F, F, w2t, 0, nullptr, s), "router/W2.T");
-    if (fwd) STAGE(launch_transpose(w2t, Kc, D, D, wcb, 1, nullptr, s, E, M), "router/W2[:,e]");
-    if (fwd) STAGE(launch_spmm_blocked(avb, amb, wcb, nullptr, rows, D, Kc, 0, Y3, D, s, &g0), "router/y3");                       // eq. (3)
+    if (fwd && !packed) {       // the rest of the weight preparation, Alg. 2 line 2 included: the backward half prepares nothing
+        STAGE(launch_transpose(W2, D, F, F, w2t, 0, nullptr, s), "router/W2.T");
+        STAGE(launch_transpose(w2t, Kc, D, D, w2e, 1, nullptr, s, E, M), "router/W2[:,e]");
+        STAGE(launch_prune24_step(w2t, F, D, D, 0, cfg->mode, w2cv, w2cm, w2cvb, w2cmb, nullptr, s, 1, M), "router/prune24(W2.T)");
+        STAGE(launch_transpose(W1, Kc, D, D, w1et, 1, nullptr, s, E, M), "router/W1[e].T");
+    }
+    if (fwd) STAGE(launch_spmm_blocked(avb, amb, w2e, nullptr, rows, D, Kc, 0, Y3, D, s, &g0), "router/y3");                       // eq. (3)
     // ---- Alg. 2 ------------------------------------------------------------------------------------------------------
-    if (bwd) STAGE(launch_prune24_step(w2t, F, D, D, 0, cfg->mode, w2cv, w2cm, w2cvb, w2cmb, nullptr, s, 1, M), "router/prune24(W2.T)");
     if (bwd) STAGE(launch_transpose(dY, rows, D, D, dypt, 0, dyb, s, 1, 0, perm), "router/dY[perm].T");
     if (bwd) STAGE(launch_venom_expand_t_compact(vals, meta, rows, Kc, at, s), "router/expand(y2)");
     // eq. (5) is computed as dW2.T [F, D] (whole 2 D-byte rows per hidden unit) and transposed: writing dW2 [D, F] directly
     // would scatter 8-byte pieces M hidden units apart
-    if (bwd) STAGE(launch_gemm_nt(0, at, nullptr, dypt, nullptr, Kc, D, rows, 0, wcb, D, s, &g2), "router/dW2.T");                 // eq. (5)
-    if (bwd) STAGE(launch_transpose(wcb, F, D, D, dW2, 0, nullptr, s), "router/dW2");
+    if (bwd) STAGE(launch_gemm_nt(0, at, nullptr, dypt, nullptr, Kc, D, rows, 0, dw2t, D, s, &g2), "router/dW2.T");                 // eq. (5)
+    if (bwd) STAGE(launch_transpose(dw2t, F, D, D, dW2, 0, nullptr, s), "router/dW2");
     if (bwd) {   // eq. (4) at the expert's hidden units, then eq. (6) on y2's slots while the tile is in LDS; dy2c itself only on request
         GemmGroup g4 = g1;
         g4.bias_stride = 0;
@@ -923,8 +931,7 @@ static int run_router_step(const sffn_cfg* cfg, const int64_t* seg_offsets, cons
         ep.mode = 4; ep.store_dense = (cfg->flags & SFFN_FLAG_KEEP_DENSE) ? 1 : 0; ep.vals = dvals; ep.meta = meta; ep.ykept = y1c; ep.v24 = avb;
         STAGE(launch_gemm_vnm_epilogue(w2cvb, w2cmb, dyb, nullptr, Kc, rows, D, dy2c, ep, s, &g4), "router/dy2c+dsqrelu");
     }
-    if (bwd) STAGE(launch_transpose(W1, Kc, D, D, wcb, 1, nullptr, s, E, M), "router/W1[e].T");
-    if (bwd) STAGE(launch_spmm_blocked(avb, amb, wcb, nullptr, rows, D, Kc, 0, dX, D, s, &g0), "router/dX");                       // eq. (7)
+    if (bwd) STAGE(launch_spmm_blocked(avb, amb, w1et, nullptr, rows, D, Kc, 0, dX, D, s, &g0), "router/dX");                       // eq. (7)
     if (bwd) STAGE(launch_venom_expand_t_compact(dvals, meta, rows, Kc, at, s), "router/expand(dy1)");
     if (bwd) STAGE(launch_gemm_nt(0, at, nullptr, xpt, nullptr, Kc, D, rows, 0, dW1, D, s, &g2), "router/dW1");                    // eq. (8)
     return SFFN_OK;
@@ -943,10 +950,10 @@ int ffn_router_forward(const sffn_cfg* cfg, const int64_t* seg_offsets, const in
     REQUIRE(seg_offsets, SFFN_EINVAL, "ffn_router_forward: null pointer");
     return run_router_step(cfg, seg_offsets, nullptr, perm, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, workspace, ws_bytes, stream, false, 1);
 }
-int ffn_router_backward(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* W1, const uint16_t* dY,
-                        uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
+int ffn_router_backward(const sffn_cfg* cfg, const int64_t* seg_offsets, const int32_t* perm, const uint16_t* dY, uint16_t* dX, uint16_t* dW1,
+                        uint16_t* dW2, void* workspace, size_t ws_bytes, void* stream) {
     REQUIRE(seg_offsets, SFFN_EINVAL, "ffn_router_backward: null pointer");
-    return run_router_step(cfg, seg_offsets, nullptr, perm, nullptr, W1, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, stream, false, 2);
+    return run_router_step(cfg, seg_offsets, nullptr, perm, nullptr, nullptr, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, stream, false, 2);
 }
 
 // Routing buffers of ffn_router_full_step, behind the step's own workspace: expert [T], perm [rows], row_of_token [T],
@@ -1010,9 +1017,9 @@ int ffn_router_full_forward(const sffn_cfg* cfg, const uint16_t* means, const ui
                             const float* b1, uint16_t* Y3, void* workspace, size_t ws_bytes, void* stream) {
     return run_router_full(cfg, means, X, W1, W2, b1, nullptr, Y3, nullptr, nullptr, nullptr, workspace, ws_bytes, stream, 1);
 }
-int ffn_router_full_backward(const sffn_cfg* cfg, const uint16_t* W1, const uint16_t* dY, uint16_t* dX, uint16_t* dW1, uint16_t* dW2,
-                             void* workspace, size_t ws_bytes, void* stream) {
-    return run_router_full(cfg, nullptr, nullptr, W1, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, stream, 2);
+int ffn_router_full_backward(const sffn_cfg* cfg, const uint16_t* dY, uint16_t* dX, uint16_t* dW1, uint16_t* dW2, void* workspace, size_t ws_bytes,
+                             void* stream) {
+    return run_router_full(cfg, nullptr, nullptr, nullptr, nullptr, nullptr, dY, nullptr, dX, dW1, dW2, workspace, ws_bytes, stream, 2);
 }
 
 // Alg. 1 + Alg. 2 for n_experts independent FFNs over consecutive token segments (n_experts = 1, seg = nullptr:

@@ -183,7 +183,7 @@ def test_router_entry_points_validate_on_the_host():
     assert lib.ffn_router_step(ctypes.byref(bad), ok, *args, fake, big, None) == -1
     m12 = binding._Cfg(100, 64, 1024, 64, 12, 0, 0)
     assert lib.ffn_router_step(ctypes.byref(m12), ok, *args, fake, big, None) == -2
-    assert lib.ffn_router_step(ctypes.byref(binding._Cfg(cfg.T, cfg.D, cfg.F, 64, cfg.M, 0, 16)), ok, *args, fake, big, None) == -2     # no packed-weights form
+    assert lib.ffn_router_step(ctypes.byref(binding._Cfg(cfg.T, cfg.D, cfg.F, 64, cfg.M, 0, 16)), ok, *args, fake, 16, None) == -3      # packed weights: accepted, the workspace is what fails
     assert lib.ffn_router_step(ctypes.byref(binding._Cfg(cfg.T, cfg.D, cfg.F, 64, cfg.M, 0, 32)), ok, *args, fake, big, None) == -2     # no float32 accumulation
     assert lib.sffn_router_full_workspace_bytes(ctypes.byref(cfg)) > lib.sffn_router_workspace_bytes(ctypes.byref(cfg))
     assert lib.sffn_router_full_workspace_bytes(ctypes.byref(bad)) == 0
@@ -193,13 +193,13 @@ def test_router_entry_points_validate_on_the_host():
     # the router's step as two calls: each half checks what it reads
     assert lib.ffn_router_forward(ctypes.byref(cfg), ok, fake, fake, fake, fake, fake, fake, fake, 16, None) == -3
     assert lib.ffn_router_forward(ctypes.byref(cfg), ok, fake, None, fake, fake, fake, fake, fake, big, None) == -1
-    assert lib.ffn_router_backward(ctypes.byref(cfg), ok, fake, fake, None, fake, fake, fake, fake, big, None) == -1
-    assert lib.ffn_router_backward(ctypes.byref(cfg), None, fake, fake, fake, fake, fake, fake, fake, big, None) == -1
-    assert lib.ffn_router_backward(ctypes.byref(m12), ok, fake, fake, fake, fake, fake, fake, fake, big, None) == -2
+    assert lib.ffn_router_backward(ctypes.byref(cfg), ok, fake, None, fake, fake, fake, fake, big, None) == -1
+    assert lib.ffn_router_backward(ctypes.byref(cfg), None, fake, fake, fake, fake, fake, fake, big, None) == -1
+    assert lib.ffn_router_backward(ctypes.byref(m12), ok, fake, fake, fake, fake, fake, fake, big, None) == -2
     assert lib.ffn_router_full_forward(ctypes.byref(cfg), None, fake, fake, fake, fake, fake, fake, big, None) == -1
     assert lib.ffn_router_full_forward(ctypes.byref(cfg), fake, fake, fake, fake, fake, fake, fake, 16, None) == -3
-    assert lib.ffn_router_full_backward(ctypes.byref(cfg), fake, None, fake, fake, fake, fake, big, None) == -1
-    assert lib.ffn_router_full_backward(ctypes.byref(cfg), fake, fake, fake, fake, fake, fake, 16, None) == -3
+    assert lib.ffn_router_full_backward(ctypes.byref(cfg), None, fake, fake, fake, fake, big, None) == -1
+    assert lib.ffn_router_full_backward(ctypes.byref(cfg), fake, fake, fake, fake, fake, 16, None) == -3
 
 
 def test_lean_workspace_has_no_room_for_the_copies_it_does_not_write():

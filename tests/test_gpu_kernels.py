@@ -669,10 +669,21 @@ def test_ffn_router_step_against_oracle(M, mode, T, D, F):
     y3_a = to_bits(two.forward(route, dev["X"], dev["W1"], dev["W2"], dev["b1"])).copy()
     y3_b = to_bits(two_full.full_forward(dev["means"], dev["X"], dev["W1"], dev["W2"], dev["b1"])).copy()
     one.full(dev["means"], torch.flip(dev["X"], (0,)).contiguous(), dev["W1"], dev["W2"], dev["b1"], dev["dY"])
-    g_b = [to_bits(t).copy() for t in two_full.full_backward(dev["W1"], dev["dY"])]
-    g_a = [to_bits(t).copy() for t in two.backward(route, dev["W1"], dev["dY"])]
+    g_b = [to_bits(t).copy() for t in two_full.full_backward(dev["dY"])]
+    g_a = [to_bits(t).copy() for t in two.backward(route, dev["dY"])]
     assert np.array_equal(y3_a, Y3) and np.array_equal(y3_b, Y3)
     assert all(np.array_equal(a, b) for a, b in zip(g_a, (dX, dW1, dW2))) and all(np.array_equal(a, b) for a, b in zip(g_b, (dX, dW1, dW2)))
+    # a second micro-batch on the weights the first call prepared (SFFN_FLAG_WEIGHTS_PACKED): the five weight-preparation launches are
+    # skipped - the weights handed over are garbage and go unread - and the results are those of a full call on the same tensors
+    X2, dY2 = torch.flip(dev["X"], (0,)).contiguous(), torch.flip(dev["dY"], (0,)).contiguous()
+    junk1, junk2 = torch.full_like(dev["W1"], 3.0), torch.full_like(dev["W2"], -2.0)
+    want2 = [to_bits(t).copy() for t in one.full(dev["means"], X2, dev["W1"], dev["W2"], dev["b1"], dY2)]
+    got2 = [to_bits(t).copy() for t in two_full.full(dev["means"], X2, junk1, junk2, dev["b1"], dY2, weights_packed=True)]
+    assert all(np.array_equal(a, b) for a, b in zip(got2, want2))
+    route2 = sffn.venom_route(X2, dev["means"], M)
+    y3_c = to_bits(two.forward(route2, X2, junk1, junk2, dev["b1"], weights_packed=True)).copy()
+    g_c = [to_bits(t).copy() for t in two.backward(route2, dY2)]
+    assert np.array_equal(y3_c, want2[0]) and all(np.array_equal(a, b) for a, b in zip(g_c, want2[1:]))
     expert = oracle.route_top1(oracle.route_scores(inp["X"], inp["means"]))
     perm, seg = oracle.expert_permutation(expert, M // 4)
     assert np.array_equal(to_bits(route["perm"]), perm) and route["seg"] == [int(v) for v in seg]
